@@ -1,0 +1,702 @@
+/*
+ * goom_oracle.c -- plain CPU oracle for generalized orders of magnitude (GOOMs).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement of
+ * what the GPU library must compute.  It is not part of the product: nothing in the
+ * product path may include, link, import or call it, and it shares no code, header,
+ * table or constant with the HIP sources.
+ *
+ * Everything here is written from the paper's definitions:
+ *   - a GOOM is a complex logarithm x' with exp(x') real; Re = log|x|, Im = an even
+ *     multiple of pi for x >= 0 and an odd multiple for x < 0; zero is non-negative
+ *     (Section 2, eq. 1 and the paragraph after it);
+ *   - float -> GOOM and GOOM -> float maps (Section 3.1);
+ *   - LMME(A', B') = log(exp(A') exp(B')) = LSE_j(A'_ij + B'_jk) (Section 3.2, eq. 6),
+ *     written here in its definitional signed log-sum-exp form (Example 2), never the
+ *     scaled-matmul shortcut of eq. 7;
+ *   - matrix-product chains S'_t = LMME(A'_t, S'_{t-1}) (Section 4.1);
+ *   - the linear recurrence with bias used for non-diagonal state-space models
+ *     (Section 4.3, eqs. 18 and 20);
+ *   - sequential QR estimation of Lyapunov spectra (Section 4.2.1, eqs. 12-13) and
+ *     the selectively reset recurrence (Section 5; Appendix C).
+ *
+ * Arithmetic: log-magnitudes are held in IEEE double, signs as one byte (0 = +, 1 = -).
+ * Sums of exponentials accumulate in long double.  Codecs evaluate log/exp in
+ * __float128 and round once to the component type, so they are correctly rounded for
+ * every practical purpose.  OpenMP is used only across independent outputs of one
+ * combine or across independent problems; every chain is walked strictly left to
+ * right in t.
+ *
+ * Pins (tests/test_oracle_*.py, run without a GPU): closed forms and the paper's
+ * printed examples for the codecs; brute-force extended-precision real products,
+ * the exp(1000) dot-product example, shift/permutation invariances and d = 1 for
+ * LMME; brute force, the worked scan of Appendix C and the Gaussian growth-rate
+ * closed form for the scan; brute force and degenerate cases for the affine
+ * recurrence; the Appendix C reset example, S == 0, the log|det| sum rule and the
+ * Gaussian closed-form spectrum for the reset recurrence and the QR estimator.
+ */
+#include <math.h>
+#include <quadmath.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#include <float.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_API __attribute__((visibility("default")))
+
+/* ------------------------------------------------------------------------- */
+/* threads                                                                    */
+/* ------------------------------------------------------------------------- */
+
+ORACLE_API int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+ORACLE_API void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* ------------------------------------------------------------------------- */
+/* codecs (Section 3.1)                                                       */
+/* ------------------------------------------------------------------------- */
+
+/* Sign of the real number a GOOM stands for: negative iff Im is an odd multiple of
+ * pi (Section 2).  Rounding Im/pi to the nearest integer accepts any representative. */
+static inline uint8_t sign_from_imag(double im)
+{
+    long long k = llround(im / M_PI);
+    return (uint8_t)(k & 1LL);
+}
+
+/* Finite floor for log 0: twice the log of the smallest normal number of the
+ * component format (Section 3.1, footnote on the configurable real log). */
+static float floor_f32(void) { return (float)(2.0Q * logq((__float128)FLT_MIN)); }
+static double floor_f64(void) { return (double)(2.0Q * logq((__float128)DBL_MIN)); }
+
+ORACLE_API float oracle_floor_f32(void) { return floor_f32(); }
+ORACLE_API double oracle_floor_f64(void) { return floor_f64(); }
+
+/* x -> (log|x|, 0 or pi), interleaved (re, im).  zero_floor = 0: log 0 = -inf;
+ * zero_floor = 1: log 0 = the finite floor.  -0.0 counts as non-negative. */
+ORACLE_API void oracle_to_goom_f32(const float *x, float *y, size_t n, int zero_floor)
+{
+    const float pi_f = (float)M_PIq;
+    const float fl = floor_f32();
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        float v = x[i];
+        float re;
+        if (v == 0.0f)
+            re = zero_floor ? fl : -INFINITY;
+        else
+            re = (float)logq(fabsq((__float128)v)); /* NaN -> NaN, +-inf -> +inf */
+        y[2 * i] = re;
+        y[2 * i + 1] = (v < 0.0f) ? pi_f : 0.0f;
+    }
+}
+
+ORACLE_API void oracle_to_goom_f64(const double *x, double *y, size_t n, int zero_floor)
+{
+    const double pi_d = (double)M_PIq;
+    const double fl = floor_f64();
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        double v = x[i];
+        double re;
+        if (v == 0.0)
+            re = zero_floor ? fl : -INFINITY;
+        else
+            re = (double)logq(fabsq((__float128)v));
+        y[2 * i] = re;
+        y[2 * i + 1] = (v < 0.0) ? pi_d : 0.0;
+    }
+}
+
+/* (re, im) -> Re(exp(re + i im)) = +-exp(re); the imaginary part of the complex
+ * exponential is dropped (Section 3.1, eq. 4). */
+ORACLE_API void oracle_from_goom_f32(const float *y, float *x, size_t n)
+{
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        __float128 e = expq((__float128)y[2 * i]);
+        float mag = (float)e;
+        x[i] = sign_from_imag((double)y[2 * i + 1]) ? -mag : mag;
+    }
+}
+
+ORACLE_API void oracle_from_goom_f64(const double *y, double *x, size_t n)
+{
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        __float128 e = expq((__float128)y[2 * i]);
+        double mag = (double)e;
+        x[i] = sign_from_imag(y[2 * i + 1]) ? -mag : mag;
+    }
+}
+
+/* Widen interleaved complex GOOMs to the oracle's working form: double
+ * log-magnitude plus a sign byte. */
+ORACLE_API void oracle_split_c64(const float *z, double *re, uint8_t *sg, size_t n)
+{
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        re[i] = (double)z[2 * i];
+        sg[i] = sign_from_imag((double)z[2 * i + 1]);
+    }
+}
+
+ORACLE_API void oracle_split_c128(const double *z, double *re, uint8_t *sg, size_t n)
+{
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        re[i] = z[2 * i];
+        sg[i] = sign_from_imag(z[2 * i + 1]);
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* signed log-sum-exp (Example 2) and LMME (Section 3.2, eq. 6)               */
+/* ------------------------------------------------------------------------- */
+
+/* log of sum_j (+-)exp(z_j).  Returns the log-magnitude, the sign, and
+ * kappa = sum_j exp(z_j) / |sum_j (+-)exp(z_j)|, the cancellation factor of the sum
+ * (1 = no cancellation).  An empty or all -inf sum is zero: (-inf, +). */
+static void signed_lse(int d, const double *z, const uint8_t *s, double *out_re,
+                       uint8_t *out_sg, double *out_kappa)
+{
+    double m = -INFINITY;
+    for (int j = 0; j < d; ++j)
+        if (z[j] > m) m = z[j];
+    if (!(m > -INFINITY)) {
+        *out_re = -INFINITY;
+        *out_sg = 0;
+        if (out_kappa) *out_kappa = 1.0;
+        return;
+    }
+    long double acc = 0.0L, mass = 0.0L;
+    for (int j = 0; j < d; ++j) {
+        long double e = expl((long double)(z[j] - m));
+        mass += e;
+        acc += s[j] ? -e : e;
+    }
+    if (acc == 0.0L) {
+        *out_re = -INFINITY;
+        *out_sg = 0;
+        if (out_kappa) *out_kappa = INFINITY;
+        return;
+    }
+    *out_re = m + (double)logl(fabsl(acc));
+    *out_sg = acc < 0.0L;
+    if (out_kappa) *out_kappa = (double)(mass / fabsl(acc));
+}
+
+/* C' = LMME(A', B'):  C'_ik = LSE_j(A'_ij + B'_jk), A' is n x d, B' is d x m, all
+ * row-major.  Adding two GOOMs adds log-magnitudes and xors signs (Example 1).
+ * kappa may be NULL. */
+ORACLE_API void oracle_lmme(const double *are, const uint8_t *asg, const double *bre,
+                            const uint8_t *bsg, double *cre, uint8_t *csg, double *kappa,
+                            int n, int d, int m)
+{
+#pragma omp parallel
+    {
+        double *z = (double *)malloc(sizeof(double) * (size_t)(d > 0 ? d : 1));
+        uint8_t *s = (uint8_t *)malloc((size_t)(d > 0 ? d : 1));
+#pragma omp for collapse(2) schedule(static)
+        for (int i = 0; i < n; ++i) {
+            for (int k = 0; k < m; ++k) {
+                for (int j = 0; j < d; ++j) {
+                    z[j] = are[(size_t)i * d + j] + bre[(size_t)j * m + k];
+                    /* (-inf) + (+inf) would be NaN; a zero factor makes the term zero */
+                    if (are[(size_t)i * d + j] == -INFINITY || bre[(size_t)j * m + k] == -INFINITY)
+                        z[j] = -INFINITY;
+                    s[j] = asg[(size_t)i * d + j] ^ bsg[(size_t)j * m + k];
+                }
+                signed_lse(d, z, s, &cre[(size_t)i * m + k], &csg[(size_t)i * m + k],
+                           kappa ? &kappa[(size_t)i * m + k] : NULL);
+            }
+        }
+        free(z);
+        free(s);
+    }
+}
+
+/* batch of independent LMMEs, leading index first (Section 3: functions broadcast
+ * over preceding indices). */
+ORACLE_API void oracle_lmme_batched(const double *are, const uint8_t *asg, const double *bre,
+                                    const uint8_t *bsg, double *cre, uint8_t *csg,
+                                    double *kappa, long batch, int n, int d, int m)
+{
+    for (long b = 0; b < batch; ++b)
+        oracle_lmme(are + (size_t)b * n * d, asg + (size_t)b * n * d, bre + (size_t)b * d * m,
+                    bsg + (size_t)b * d * m, cre + (size_t)b * n * m, csg + (size_t)b * n * m,
+                    kappa ? kappa + (size_t)b * n * m : NULL, n, d, m);
+}
+
+/* ------------------------------------------------------------------------- */
+/* chain of matrix products (Section 4.1, eqs. 8-9)                           */
+/* ------------------------------------------------------------------------- */
+
+/* Inclusive prefix products, newer factor on the left:
+ *   P_1 = M_1 (or LMME(M_1, init) when init is given, init being d x m),
+ *   P_t = LMME(M_t, P_{t-1}),  t = 2..T.
+ * M is [T, d, d]; P is [T, d, m] (m = d when init is NULL); kappa (nullable, same
+ * shape as P) receives the cancellation factor of the last sum that produced each
+ * entry (1 for entries copied from M_1). */
+ORACLE_API void oracle_scan(const double *mre, const uint8_t *msg, const double *ire,
+                            const uint8_t *isg, double *pre, uint8_t *psg, double *kappa,
+                            long T, int d, int m)
+{
+    size_t dd = (size_t)d * d, dm = (size_t)d * m;
+    for (long t = 0; t < T; ++t) {
+        const double *pr_prev;
+        const uint8_t *ps_prev;
+        if (t == 0) {
+            if (!ire) {
+                memcpy(pre, mre, sizeof(double) * dd);
+                memcpy(psg, msg, dd);
+                if (kappa)
+                    for (size_t e = 0; e < dd; ++e) kappa[e] = 1.0;
+                continue;
+            }
+            pr_prev = ire;
+            ps_prev = isg;
+        } else {
+            pr_prev = pre + (size_t)(t - 1) * dm;
+            ps_prev = psg + (size_t)(t - 1) * dm;
+        }
+        oracle_lmme(mre + (size_t)t * dd, msg + (size_t)t * dd, pr_prev, ps_prev,
+                    pre + (size_t)t * dm, psg + (size_t)t * dm,
+                    kappa ? kappa + (size_t)t * dm : NULL, d, d, m);
+    }
+}
+
+/* Same chain, but only the running state is kept; the caller passes the state in
+ * (state_valid != 0) or starts a fresh chain (state_valid == 0: the state becomes
+ * M_1).  After the call the state is P_T.  Steps listed in sample_t (0-based,
+ * ascending, nsample entries) are copied to out (nsample x d x m).  Lets a long chain
+ * be walked block by block without holding every prefix. */
+ORACLE_API void oracle_scan_stream(const double *mre, const uint8_t *msg, double *state_re,
+                                   uint8_t *state_sg, int state_valid, const long *sample_t,
+                                   long nsample, double *out_re, uint8_t *out_sg,
+                                   double *out_kappa, long T, int d, int m)
+{
+    size_t dd = (size_t)d * d, dm = (size_t)d * m;
+    double *nre = (double *)malloc(sizeof(double) * dm);
+    uint8_t *nsg = (uint8_t *)malloc(dm);
+    double *nk = (double *)malloc(sizeof(double) * dm);
+    long si = 0;
+    for (long t = 0; t < T; ++t) {
+        if (t == 0 && !state_valid) {
+            memcpy(nre, mre, sizeof(double) * dd);
+            memcpy(nsg, msg, dd);
+            for (size_t e = 0; e < dd; ++e) nk[e] = 1.0;
+        } else {
+            oracle_lmme(mre + (size_t)t * dd, msg + (size_t)t * dd, state_re, state_sg, nre,
+                        nsg, nk, d, d, m);
+        }
+        memcpy(state_re, nre, sizeof(double) * dm);
+        memcpy(state_sg, nsg, dm);
+        while (si < nsample && sample_t[si] == t) {
+            memcpy(out_re + (size_t)si * dm, nre, sizeof(double) * dm);
+            memcpy(out_sg + (size_t)si * dm, nsg, dm);
+            if (out_kappa) memcpy(out_kappa + (size_t)si * dm, nk, sizeof(double) * dm);
+            ++si;
+        }
+    }
+    free(nre);
+    free(nsg);
+    free(nk);
+}
+
+/* ------------------------------------------------------------------------- */
+/* second chain oracle: scaled real products in double                        */
+/* ------------------------------------------------------------------------- */
+
+/* The same chain computed another way, for chains too long for d^3 exponentials per
+ * step: the state is a real double matrix W with one power-of-two exponent per
+ * column, P_t[:, k] = W[:, k] * 2^e_k.  Each step exponentiates the incoming factor
+ * (entries of M_t must themselves be in double range, which holds for GOOMs of
+ * ordinary floats), multiplies, and renormalises every column by an exact power of
+ * two.  It is trusted only after tests show it agrees with oracle_scan; it also
+ * reports kappa like oracle_scan.  State arrays: w [d*m] doubles, e [m] doubles
+ * (integer valued).  state_valid == 0 starts from P_1 = M_1 (needs m == d). */
+ORACLE_API void oracle_scan_scaled_stream(const double *mre, const uint8_t *msg, double *w,
+                                          double *e, int state_valid, const long *sample_t,
+                                          long nsample, double *out_re, uint8_t *out_sg,
+                                          double *out_kappa, long T, int d, int m)
+{
+    size_t dd = (size_t)d * d, dm = (size_t)d * m;
+    double *a = (double *)malloc(sizeof(double) * dd);
+    double *nw = (double *)malloc(sizeof(double) * dm);
+    double *nk = (double *)malloc(sizeof(double) * dm);
+    long si = 0;
+    for (long t = 0; t < T; ++t) {
+        const double *re = mre + (size_t)t * dd;
+        const uint8_t *sg = msg + (size_t)t * dd;
+        for (size_t q = 0; q < dd; ++q) {
+            double v = exp(re[q]);
+            a[q] = sg[q] ? -v : v;
+        }
+        if (t == 0 && !state_valid) {
+            memcpy(nw, a, sizeof(double) * dd);
+            for (size_t q = 0; q < dm; ++q) nk[q] = 1.0;
+            for (int k = 0; k < m; ++k) e[k] = 0.0;
+        } else {
+#pragma omp parallel for collapse(2) schedule(static)
+            for (int i = 0; i < d; ++i) {
+                for (int k = 0; k < m; ++k) {
+                    long double acc = 0.0L, mass = 0.0L;
+                    for (int j = 0; j < d; ++j) {
+                        long double p = (long double)a[(size_t)i * d + j] * w[(size_t)j * m + k];
+                        acc += p;
+                        mass += fabsl(p);
+                    }
+                    nw[(size_t)i * m + k] = (double)acc;
+                    nk[(size_t)i * m + k] = acc != 0.0L ? (double)(mass / fabsl(acc)) : INFINITY;
+                }
+            }
+        }
+        /* exact power-of-two renormalisation of every column */
+        for (int k = 0; k < m; ++k) {
+            double cmax = 0.0;
+            for (int i = 0; i < d; ++i) {
+                double v = fabs(nw[(size_t)i * m + k]);
+                if (v > cmax) cmax = v;
+            }
+            if (cmax > 0.0 && isfinite(cmax)) {
+                int ex;
+                frexp(cmax, &ex);
+                for (int i = 0; i < d; ++i) nw[(size_t)i * m + k] = ldexp(nw[(size_t)i * m + k], -ex);
+                e[k] += (double)ex;
+            }
+        }
+        memcpy(w, nw, sizeof(double) * dm);
+        while (si < nsample && sample_t[si] == t) {
+            for (int i = 0; i < d; ++i)
+                for (int k = 0; k < m; ++k) {
+                    double v = w[(size_t)i * m + k];
+                    size_t o = (size_t)si * dm + (size_t)i * m + k;
+                    out_re[o] = (v == 0.0) ? -INFINITY : log(fabs(v)) + e[k] * M_LN2;
+                    out_sg[o] = v < 0.0;
+                    if (out_kappa) out_kappa[o] = nk[(size_t)i * m + k];
+                }
+            ++si;
+        }
+    }
+    free(a);
+    free(nw);
+    free(nk);
+}
+
+/* ------------------------------------------------------------------------- */
+/* linear recurrence with bias over GOOMs (Section 4.3, eqs. 18 and 20)       */
+/* ------------------------------------------------------------------------- */
+
+/* h_t = A_t h_{t-1} + b_t, t = 1..T, h_0 given (NULL = zero vector).
+ * In GOOM form each entry of h_t is the signed log-sum-exp of the d products
+ * A'_t[i, j] + h'_{t-1}[j] together with b'_t[i]; that is eq. 20 with the inner LMMEs
+ * written out.  A is [T, d, d], b is [T, d], h is [T, d]. */
+ORACLE_API void oracle_affine_scan(const double *are, const uint8_t *asg, const double *bre,
+                                   const uint8_t *bsg, const double *h0re, const uint8_t *h0sg,
+                                   double *hre, uint8_t *hsg, double *kappa, long T, int d)
+{
+    double *pre = (double *)malloc(sizeof(double) * (size_t)d);
+    uint8_t *psg = (uint8_t *)malloc((size_t)d);
+    double *z = (double *)malloc(sizeof(double) * (size_t)(d + 1));
+    uint8_t *s = (uint8_t *)malloc((size_t)(d + 1));
+    for (int j = 0; j < d; ++j) {
+        pre[j] = h0re ? h0re[j] : -INFINITY;
+        psg[j] = h0sg ? h0sg[j] : 0;
+    }
+    for (long t = 0; t < T; ++t) {
+        const double *ar = are + (size_t)t * d * d;
+        const uint8_t *as = asg + (size_t)t * d * d;
+        for (int i = 0; i < d; ++i) {
+            for (int j = 0; j < d; ++j) {
+                z[j] = ar[(size_t)i * d + j] + pre[j];
+                if (ar[(size_t)i * d + j] == -INFINITY || pre[j] == -INFINITY) z[j] = -INFINITY;
+                s[j] = as[(size_t)i * d + j] ^ psg[j];
+            }
+            z[d] = bre[(size_t)t * d + i];
+            s[d] = bsg[(size_t)t * d + i];
+            signed_lse(d + 1, z, s, &hre[(size_t)t * d + i], &hsg[(size_t)t * d + i],
+                       kappa ? &kappa[(size_t)t * d + i] : NULL);
+        }
+        memcpy(pre, hre + (size_t)t * d, sizeof(double) * (size_t)d);
+        memcpy(psg, hsg + (size_t)t * d, (size_t)d);
+    }
+    free(pre);
+    free(psg);
+    free(z);
+    free(s);
+}
+
+/* Independent sequences, leading index first: A [batch, T, d, d], b [batch, T, d],
+ * h0 [batch, d] (nullable), h [batch, T, d].  Threads split the sequences; each
+ * sequence is still walked left to right. */
+ORACLE_API void oracle_affine_scan_batched(const double *are, const uint8_t *asg,
+                                           const double *bre, const uint8_t *bsg,
+                                           const double *h0re, const uint8_t *h0sg, double *hre,
+                                           uint8_t *hsg, double *kappa, long batch, long T, int d)
+{
+#pragma omp parallel for schedule(dynamic)
+    for (long q = 0; q < batch; ++q) {
+        size_t oa = (size_t)q * T * d * d, ob = (size_t)q * T * d;
+        oracle_affine_scan(are + oa, asg + oa, bre + ob, bsg + ob,
+                           h0re ? h0re + (size_t)q * d : NULL, h0sg ? h0sg + (size_t)q * d : NULL,
+                           hre + ob, hsg + ob, kappa ? kappa + ob : NULL, T, d);
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* QR (Householder, R_ii > 0) on small real matrices                          */
+/* ------------------------------------------------------------------------- */
+
+/* a: d x d row-major, overwritten by Q (orthonormal columns); r receives the upper
+ * triangular factor with positive diagonal.  Householder reflections, then Q is
+ * accumulated explicitly; signs are flipped at the end so that diag(R) > 0. */
+static void qr_householder(double *a, double *r, int d)
+{
+    double *q = (double *)calloc((size_t)d * d, sizeof(double));
+    double *v = (double *)malloc(sizeof(double) * (size_t)d);
+    for (int i = 0; i < d; ++i) q[(size_t)i * d + i] = 1.0;
+    /* reduce a to upper triangular in place: a <- H_k ... H_1 a ; q <- q H_1 ... H_k */
+    for (int k = 0; k < d; ++k) {
+        long double nrm = 0.0L;
+        for (int i = k; i < d; ++i) nrm += (long double)a[(size_t)i * d + k] * a[(size_t)i * d + k];
+        double alpha = (double)sqrtl(nrm);
+        if (alpha == 0.0) continue;
+        if (a[(size_t)k * d + k] > 0.0) alpha = -alpha;
+        for (int i = 0; i < d; ++i) v[i] = 0.0;
+        for (int i = k; i < d; ++i) v[i] = a[(size_t)i * d + k];
+        v[k] -= alpha;
+        long double vn = 0.0L;
+        for (int i = k; i < d; ++i) vn += (long double)v[i] * v[i];
+        if (vn == 0.0L) continue;
+        for (int j = 0; j < d; ++j) { /* a <- (I - 2 v v^T / v^T v) a */
+            long double dot = 0.0L;
+            for (int i = k; i < d; ++i) dot += (long double)v[i] * a[(size_t)i * d + j];
+            double f = (double)(2.0L * dot / vn);
+            for (int i = k; i < d; ++i) a[(size_t)i * d + j] -= f * v[i];
+        }
+        for (int i = 0; i < d; ++i) { /* q <- q (I - 2 v v^T / v^T v) */
+            long double dot = 0.0L;
+            for (int j = k; j < d; ++j) dot += (long double)q[(size_t)i * d + j] * v[j];
+            double f = (double)(2.0L * dot / vn);
+            for (int j = k; j < d; ++j) q[(size_t)i * d + j] -= f * v[j];
+        }
+    }
+    for (int i = 0; i < d; ++i)
+        for (int j = 0; j < d; ++j) r[(size_t)i * d + j] = (j >= i) ? a[(size_t)i * d + j] : 0.0;
+    for (int k = 0; k < d; ++k) {
+        if (r[(size_t)k * d + k] < 0.0) {
+            for (int j = 0; j < d; ++j) r[(size_t)k * d + j] = -r[(size_t)k * d + j];
+            for (int i = 0; i < d; ++i) q[(size_t)i * d + k] = -q[(size_t)i * d + k];
+        }
+    }
+    memcpy(a, q, sizeof(double) * (size_t)d * d);
+    free(q);
+    free(v);
+}
+
+ORACLE_API void oracle_qr(const double *a, double *q, double *r, int d)
+{
+    memcpy(q, a, sizeof(double) * (size_t)d * d);
+    qr_householder(q, r, d);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Lyapunov spectrum, sequential QR (Section 4.2.1, eqs. 12-13)               */
+/* ------------------------------------------------------------------------- */
+
+/* J: [T, d, d] real Jacobians (double).  Q_0 = I.  S_t = J_t Q_{t-1};
+ * Q_t, R_t = QR(S_t); lambda = sum_t log|diag R_t| / (dt T). */
+ORACLE_API void oracle_lyapunov_qr(const double *J, long T, int d, double dt, double *lambda)
+{
+    size_t dd = (size_t)d * d;
+    double *q = (double *)calloc(dd, sizeof(double));
+    double *s = (double *)malloc(sizeof(double) * dd);
+    double *r = (double *)malloc(sizeof(double) * dd);
+    long double *acc = (long double *)calloc((size_t)d, sizeof(long double));
+    for (int i = 0; i < d; ++i) q[(size_t)i * d + i] = 1.0;
+    for (long t = 0; t < T; ++t) {
+        const double *jt = J + (size_t)t * dd;
+        for (int i = 0; i < d; ++i)
+            for (int k = 0; k < d; ++k) {
+                long double a = 0.0L;
+                for (int j = 0; j < d; ++j) a += (long double)jt[(size_t)i * d + j] * q[(size_t)j * d + k];
+                s[(size_t)i * d + k] = (double)a;
+            }
+        qr_householder(s, r, d);
+        memcpy(q, s, sizeof(double) * dd);
+        for (int k = 0; k < d; ++k) acc[k] += logl(fabsl((long double)r[(size_t)k * d + k]));
+    }
+    for (int k = 0; k < d; ++k) lambda[k] = (double)(acc[k] / ((long double)dt * (long double)T));
+    free(q);
+    free(s);
+    free(r);
+    free(acc);
+}
+
+/* ------------------------------------------------------------------------- */
+/* selectively reset recurrence (Section 5; Section 4.2.1 item (a))           */
+/* ------------------------------------------------------------------------- */
+
+/* Log-normalise the columns of a GOOM matrix to unit norm, exponentiate, and
+ * return the real matrix plus each column's log-norm (Section 4.2.1 (a): states are
+ * log-scaled to log-unit norms over GOOMs before QR).  A zero column keeps
+ * log-norm -inf and exponentiates to zeros. */
+static void normalise_columns(const double *xre, const uint8_t *xsg, double *n, double *lognorm,
+                              int d)
+{
+    for (int k = 0; k < d; ++k) {
+        double m = -INFINITY;
+        for (int i = 0; i < d; ++i)
+            if (xre[(size_t)i * d + k] > m) m = xre[(size_t)i * d + k];
+        if (!(m > -INFINITY)) {
+            lognorm[k] = -INFINITY;
+            for (int i = 0; i < d; ++i) n[(size_t)i * d + k] = 0.0;
+            continue;
+        }
+        long double ss = 0.0L;
+        for (int i = 0; i < d; ++i) ss += expl(2.0L * (long double)(xre[(size_t)i * d + k] - m));
+        lognorm[k] = m + 0.5 * (double)logl(ss);
+        for (int i = 0; i < d; ++i) {
+            double v = exp(xre[(size_t)i * d + k] - lognorm[k]);
+            n[(size_t)i * d + k] = xsg[(size_t)i * d + k] ? -v : v;
+        }
+    }
+}
+
+/* Selection function of Section 4.2.1 (a): 1 when the absolute cosine similarity of
+ * any pair of (unit) columns exceeds the threshold. */
+static int near_colinear(const double *n, int d, double threshold)
+{
+    for (int a = 0; a < d; ++a)
+        for (int b = a + 1; b < d; ++b) {
+            long double dot = 0.0L;
+            for (int i = 0; i < d; ++i) dot += (long double)n[(size_t)i * d + a] * n[(size_t)i * d + b];
+            if (fabsl(dot) > threshold) return 1;
+        }
+    return 0;
+}
+
+/* X_t = J_t X_{t-1}, t = 1..T, over GOOMs, with the state examined at every step t
+ * that is a multiple of check_every: when policy == 1 (always) or, for policy == 0,
+ * when the columns are near-colinear, the state is replaced by the orthonormal
+ * factor Q of its column-normalised real form (Section 5: X_t <- R(X_t); Section
+ * 4.2.1 (a) for this particular S and R).  With R_ii > 0, the log-growth removed by a
+ * reset from column k is log R_kk + lognorm_k; those accumulate in growth[k].  At
+ * the end the same factorisation is applied once to the final state (without
+ * replacing it) so that growth / (dt T) estimates the spectrum.  policy == -1: never
+ * reset (plain chain).
+ *   J' : [T, d, d] GOOMs;  X0 : [d, d] GOOM (NULL = identity)
+ *   states : [T, d, d] (after any reset at that step);  reset_flag : [T] bytes
+ *   growth : [d] */
+ORACLE_API void oracle_reset_scan(const double *jre, const uint8_t *jsg, const double *x0re,
+                                  const uint8_t *x0sg, double *sre, uint8_t *ssg,
+                                  uint8_t *reset_flag, double *growth, long T, int d,
+                                  long check_every, int policy, double cos_threshold)
+{
+    size_t dd = (size_t)d * d;
+    double *cre = (double *)malloc(sizeof(double) * dd);
+    uint8_t *csg = (uint8_t *)malloc(dd);
+    double *n = (double *)malloc(sizeof(double) * dd);
+    double *r = (double *)malloc(sizeof(double) * dd);
+    double *ln = (double *)malloc(sizeof(double) * (size_t)d);
+    long double *acc = (long double *)calloc((size_t)d, sizeof(long double));
+    for (int i = 0; i < d; ++i)
+        for (int k = 0; k < d; ++k) {
+            cre[(size_t)i * d + k] = x0re ? x0re[(size_t)i * d + k] : (i == k ? 0.0 : -INFINITY);
+            csg[(size_t)i * d + k] = x0sg ? x0sg[(size_t)i * d + k] : 0;
+        }
+    for (long t = 0; t < T; ++t) {
+        double *ore = sre + (size_t)t * dd;
+        uint8_t *osg = ssg + (size_t)t * dd;
+        oracle_lmme(jre + (size_t)t * dd, jsg + (size_t)t * dd, cre, csg, ore, osg, NULL, d, d, d);
+        int did = 0;
+        if (policy >= 0 && check_every > 0 && ((t + 1) % check_every) == 0) {
+            normalise_columns(ore, osg, n, ln, d);
+            if (policy == 1 || near_colinear(n, d, cos_threshold)) {
+                qr_householder(n, r, d); /* n <- Q */
+                for (int k = 0; k < d; ++k) acc[k] += logl(fabsl((long double)r[(size_t)k * d + k])) + ln[k];
+                for (size_t q = 0; q < dd; ++q) {
+                    ore[q] = n[q] == 0.0 ? -INFINITY : log(fabs(n[q]));
+                    osg[q] = n[q] < 0.0;
+                }
+                did = 1;
+            }
+        }
+        if (reset_flag) reset_flag[t] = (uint8_t)did;
+        memcpy(cre, ore, sizeof(double) * dd);
+        memcpy(csg, osg, dd);
+    }
+    if (growth) {
+        normalise_columns(cre, csg, n, ln, d);
+        qr_householder(n, r, d);
+        for (int k = 0; k < d; ++k) {
+            long double g = acc[k] + logl(fabsl((long double)r[(size_t)k * d + k])) + ln[k];
+            growth[k] = (double)g;
+        }
+    }
+    free(cre);
+    free(csg);
+    free(n);
+    free(r);
+    free(ln);
+    free(acc);
+}
+
+/* ------------------------------------------------------------------------- */
+/* the literal tuple combine of Section 5, eq. 21, over plain reals           */
+/* ------------------------------------------------------------------------- */
+
+/* One application of the selective-resetting transformation to a pair of tuples
+ * (A_prev, B_prev), (A_curr, B_curr) of real d x d matrices (double, row-major).
+ * select_prev is the value of S(A_prev) decided by the caller; reset_value is
+ * R(A_prev) (used only when the reset fires).  prev is updated in place by the
+ * reset, curr by the recurrence.  The bias update uses A_curr as it was before
+ * this step's update of A_curr, which is what the worked example in Appendix C
+ * shows (A_3 B_2 + B_3). */
+ORACLE_API void oracle_reset_combine_real(double *a_prev, double *b_prev, double *a_curr,
+                                          double *b_curr, int select_prev,
+                                          const double *reset_value, int d)
+{
+    size_t dd = (size_t)d * d;
+    int b_is_zero = 1;
+    for (size_t q = 0; q < dd; ++q)
+        if (b_prev[q] != 0.0) { b_is_zero = 0; break; }
+    if (select_prev && b_is_zero) {
+        memcpy(b_prev, reset_value, sizeof(double) * dd);
+        memset(a_prev, 0, sizeof(double) * dd);
+    }
+    double *na = (double *)malloc(sizeof(double) * dd);
+    double *nb = (double *)malloc(sizeof(double) * dd);
+    for (int i = 0; i < d; ++i)
+        for (int k = 0; k < d; ++k) {
+            long double sa = 0.0L, sb = 0.0L;
+            for (int j = 0; j < d; ++j) {
+                sa += (long double)a_curr[(size_t)i * d + j] * a_prev[(size_t)j * d + k];
+                sb += (long double)a_curr[(size_t)i * d + j] * b_prev[(size_t)j * d + k];
+            }
+            na[(size_t)i * d + k] = (double)sa;
+            nb[(size_t)i * d + k] = (double)(sb + (long double)b_curr[(size_t)i * d + k]);
+        }
+    memcpy(a_curr, na, sizeof(double) * dd);
+    memcpy(b_curr, nb, sizeof(double) * dd);
+    free(na);
+    free(nb);
+}

@@ -1,0 +1,285 @@
+"""ctypes front end of the CPU oracle (``goom_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()`` and by
+the ``cpu_baseline`` leg of ``bench.py``; never by the product package.  The module
+only marshals numpy arrays into the C functions; all arithmetic is in the C file.
+
+GOOM arrays cross this boundary in two forms:
+  * complex64 / complex128 numpy arrays (real = log-magnitude, imag = 0 or pi), the
+    storage format of the paper's implementation (Section 3);
+  * the oracle's working form ``(re, sg)``: float64 log-magnitudes and uint8 signs
+    (0 = non-negative, 1 = negative).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "goom_oracle.c")
+_LIB = os.path.join(_HERE, "libgoom_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (OpenMP, libquadmath).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-fvisibility=hidden", "-Wall",
+               _SRC, "-o", _LIB, "-lquadmath", "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.oracle_floor_f32.restype = C.c_float
+        _lib.oracle_floor_f64.restype = C.c_double
+        _lib.oracle_num_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    lib().oracle_set_num_threads(C.c_int(n))
+
+
+def floor_value(dtype) -> float:
+    return float(lib().oracle_floor_f32() if np.dtype(dtype) == np.float32 else lib().oracle_floor_f64())
+
+
+# ----------------------------------------------------------------------------- codecs
+
+def to_goom(x: np.ndarray, zero_floor: bool = False) -> np.ndarray:
+    """float32/float64 array -> complex64/complex128 GOOM array (Section 3.1)."""
+    x = np.ascontiguousarray(x)
+    if x.dtype == np.float32:
+        y = np.empty(x.shape, dtype=np.complex64)
+        lib().oracle_to_goom_f32(_p(x), _p(y), C.c_size_t(x.size), C.c_int(int(zero_floor)))
+    elif x.dtype == np.float64:
+        y = np.empty(x.shape, dtype=np.complex128)
+        lib().oracle_to_goom_f64(_p(x), _p(y), C.c_size_t(x.size), C.c_int(int(zero_floor)))
+    else:
+        raise TypeError("to_goom: float32 or float64 expected")
+    return y
+
+
+def from_goom(z: np.ndarray) -> np.ndarray:
+    """complex64/complex128 GOOM array -> float32/float64 array (Section 3.1)."""
+    z = np.ascontiguousarray(z)
+    if z.dtype == np.complex64:
+        x = np.empty(z.shape, dtype=np.float32)
+        lib().oracle_from_goom_f32(_p(z), _p(x), C.c_size_t(z.size))
+    elif z.dtype == np.complex128:
+        x = np.empty(z.shape, dtype=np.float64)
+        lib().oracle_from_goom_f64(_p(z), _p(x), C.c_size_t(z.size))
+    else:
+        raise TypeError("from_goom: complex64 or complex128 expected")
+    return x
+
+
+def split(z: np.ndarray):
+    """complex GOOM array -> (float64 log-magnitudes, uint8 signs)."""
+    z = np.ascontiguousarray(z)
+    re = np.empty(z.shape, dtype=np.float64)
+    sg = np.empty(z.shape, dtype=np.uint8)
+    if z.dtype == np.complex64:
+        lib().oracle_split_c64(_p(z), _p(re), _p(sg), C.c_size_t(z.size))
+    elif z.dtype == np.complex128:
+        lib().oracle_split_c128(_p(z), _p(re), _p(sg), C.c_size_t(z.size))
+    else:
+        raise TypeError("split: complex64 or complex128 expected")
+    return re, sg
+
+
+def _as_working(z):
+    """Accept a complex array or an (re, sg) pair."""
+    if isinstance(z, tuple):
+        return _c(z[0], np.float64), _c(z[1], np.uint8)
+    return split(z)
+
+
+# ------------------------------------------------------------------------------- LMME
+
+def lmme(a, b, return_kappa: bool = False):
+    """LMME over the last two axes; leading axes are a batch (Section 3.2, eq. 6)."""
+    are, asg = _as_working(a)
+    bre, bsg = _as_working(b)
+    n, d = are.shape[-2:]
+    d2, m = bre.shape[-2:]
+    assert d == d2 and are.shape[:-2] == bre.shape[:-2]
+    lead = are.shape[:-2]
+    batch = int(np.prod(lead)) if lead else 1
+    cre = np.empty(lead + (n, m), dtype=np.float64)
+    csg = np.empty(lead + (n, m), dtype=np.uint8)
+    kap = np.empty(lead + (n, m), dtype=np.float64) if return_kappa else None
+    lib().oracle_lmme_batched(_p(are), _p(asg), _p(bre), _p(bsg), _p(cre), _p(csg), _p(kap),
+                              C.c_long(batch), C.c_int(n), C.c_int(d), C.c_int(m))
+    return (cre, csg, kap) if return_kappa else (cre, csg)
+
+
+# ------------------------------------------------------------------------------- scan
+
+def scan(mats, init=None, return_kappa: bool = False):
+    """All prefix products P_t = M_t ... M_1 (init) of a [T, d, d] chain (Section 4.1)."""
+    mre, msg = _as_working(mats)
+    T, d, d2 = mre.shape
+    assert d == d2
+    if init is not None:
+        ire, isg = _as_working(init)
+        assert ire.shape[0] == d
+        m = ire.shape[1]
+    else:
+        ire = isg = None
+        m = d
+    pre = np.empty((T, d, m), dtype=np.float64)
+    psg = np.empty((T, d, m), dtype=np.uint8)
+    kap = np.empty((T, d, m), dtype=np.float64) if return_kappa else None
+    lib().oracle_scan(_p(mre), _p(msg), _p(ire), _p(isg), _p(pre), _p(psg), _p(kap),
+                      C.c_long(T), C.c_int(d), C.c_int(m))
+    return (pre, psg, kap) if return_kappa else (pre, psg)
+
+
+class ScanStream:
+    """Walk a long chain block by block, keeping only the running state.
+
+    ``scaled=False`` uses the definitional log-sum-exp combine; ``scaled=True`` uses
+    the scaled real-product oracle (see the C file), which is for long chains only.
+    """
+
+    def __init__(self, d: int, m: int | None = None, init=None, scaled: bool = False):
+        self.d = d
+        self.m = d if m is None else m
+        self.scaled = scaled
+        self.valid = 0
+        if scaled:
+            self.w = np.zeros((d, self.m), dtype=np.float64)
+            self.e = np.zeros((self.m,), dtype=np.float64)
+            if init is not None:
+                ire, isg = _as_working(init)
+                cmax = ire.max(axis=0)
+                cmax = np.where(np.isfinite(cmax), cmax, 0.0)
+                ex = np.ceil(cmax / np.log(2.0))
+                self.w[...] = np.where(isg.astype(bool), -1.0, 1.0) * np.exp(ire - ex * np.log(2.0))
+                self.e[...] = ex
+                self.valid = 1
+        else:
+            self.re = np.full((d, self.m), -np.inf, dtype=np.float64)
+            self.sg = np.zeros((d, self.m), dtype=np.uint8)
+            if init is not None:
+                ire, isg = _as_working(init)
+                self.re[...] = ire
+                self.sg[...] = isg
+                self.valid = 1
+
+    def advance(self, mats, sample_t=(), return_kappa: bool = False):
+        """Consume a [Tb, d, d] block; return the prefixes at block-local steps sample_t."""
+        mre, msg = _as_working(mats)
+        Tb = mre.shape[0]
+        st = np.ascontiguousarray(np.asarray(sample_t, dtype=np.int64))
+        ns = st.size
+        ore = np.empty((ns, self.d, self.m), dtype=np.float64)
+        osg = np.empty((ns, self.d, self.m), dtype=np.uint8)
+        kap = np.empty((ns, self.d, self.m), dtype=np.float64) if return_kappa else None
+        if self.scaled:
+            lib().oracle_scan_scaled_stream(_p(mre), _p(msg), _p(self.w), _p(self.e),
+                                            C.c_int(self.valid), _p(st), C.c_long(ns), _p(ore),
+                                            _p(osg), _p(kap), C.c_long(Tb), C.c_int(self.d),
+                                            C.c_int(self.m))
+        else:
+            lib().oracle_scan_stream(_p(mre), _p(msg), _p(self.re), _p(self.sg),
+                                     C.c_int(self.valid), _p(st), C.c_long(ns), _p(ore), _p(osg),
+                                     _p(kap), C.c_long(Tb), C.c_int(self.d), C.c_int(self.m))
+        self.valid = 1
+        return (ore, osg, kap) if return_kappa else (ore, osg)
+
+
+# ----------------------------------------------------------------------------- affine
+
+def affine_scan(a, b, h0=None, return_kappa: bool = False):
+    """h_t = A_t h_{t-1} + b_t over GOOMs (Section 4.3).  a: [..., T, d, d]; b: [..., T, d]."""
+    are, asg = _as_working(a)
+    bre, bsg = _as_working(b)
+    T, d = bre.shape[-2:]
+    lead = bre.shape[:-2]
+    batch = int(np.prod(lead)) if lead else 1
+    assert are.shape == lead + (T, d, d)
+    if h0 is not None:
+        h0re, h0sg = _as_working(h0)
+        assert h0re.shape == lead + (d,)
+    else:
+        h0re = h0sg = None
+    hre = np.empty(lead + (T, d), dtype=np.float64)
+    hsg = np.empty(lead + (T, d), dtype=np.uint8)
+    kap = np.empty(lead + (T, d), dtype=np.float64) if return_kappa else None
+    lib().oracle_affine_scan_batched(_p(are), _p(asg), _p(bre), _p(bsg), _p(h0re), _p(h0sg),
+                                     _p(hre), _p(hsg), _p(kap), C.c_long(batch), C.c_long(T),
+                                     C.c_int(d))
+    return (hre, hsg, kap) if return_kappa else (hre, hsg)
+
+
+# --------------------------------------------------------------------------- Lyapunov
+
+def qr(a: np.ndarray):
+    a = _c(a, np.float64)
+    d = a.shape[0]
+    q = np.empty((d, d), dtype=np.float64)
+    r = np.empty((d, d), dtype=np.float64)
+    lib().oracle_qr(_p(a), _p(q), _p(r), C.c_int(d))
+    return q, r
+
+
+def lyapunov_qr(J: np.ndarray, dt: float) -> np.ndarray:
+    """Sequential-QR Lyapunov spectrum of a [T, d, d] real Jacobian chain (Section 4.2.1)."""
+    J = _c(J, np.float64)
+    T, d, _ = J.shape
+    lam = np.empty((d,), dtype=np.float64)
+    lib().oracle_lyapunov_qr(_p(J), C.c_long(T), C.c_int(d), C.c_double(dt), _p(lam))
+    return lam
+
+
+def reset_scan(jac, x0=None, check_every: int = 0, policy: int = 1, cos_threshold: float = 0.99):
+    """Selectively reset chain X_t = J_t X_{t-1} (Section 5), states examined every
+    ``check_every`` steps.  policy: 1 = reset at every examined step, 0 = reset when
+    near-colinear, -1 = never.  Returns (re, sg, reset_flag, growth)."""
+    jre, jsg = _as_working(jac)
+    T, d, _ = jre.shape
+    if x0 is not None:
+        x0re, x0sg = _as_working(x0)
+    else:
+        x0re = x0sg = None
+    sre = np.empty((T, d, d), dtype=np.float64)
+    ssg = np.empty((T, d, d), dtype=np.uint8)
+    flag = np.zeros((T,), dtype=np.uint8)
+    growth = np.empty((d,), dtype=np.float64)
+    lib().oracle_reset_scan(_p(jre), _p(jsg), _p(x0re), _p(x0sg), _p(sre), _p(ssg), _p(flag),
+                            _p(growth), C.c_long(T), C.c_int(d), C.c_long(check_every),
+                            C.c_int(policy), C.c_double(cos_threshold))
+    return sre, ssg, flag, growth
+
+
+def reset_combine_real(a_prev, b_prev, a_curr, b_curr, select_prev: bool, reset_value):
+    """One application of the tuple transformation of Section 5 (eq. 21) on real matrices.
+    Returns the updated (a_prev, b_prev, a_curr, b_curr)."""
+    ap, bp, ac, bc = (np.array(v, dtype=np.float64, order="C") for v in (a_prev, b_prev, a_curr, b_curr))
+    rv = _c(reset_value, np.float64)
+    d = ap.shape[0]
+    lib().oracle_reset_combine_real(_p(ap), _p(bp), _p(ac), _p(bc), C.c_int(int(select_prev)),
+                                    _p(rv), C.c_int(d))
+    return ap, bp, ac, bc
