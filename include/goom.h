@@ -1,0 +1,206 @@
+/*
+ * goom.h -- C ABI of libgoom: parallel prefix scans over chains of real matrices held
+ * as generalized orders of magnitude (GOOMs), for one AMD MI355X (gfx950).
+ *
+ * A GOOM is a complex logarithm x' of a real number x = exp(x'): the real part is
+ * log|x|, the imaginary part is 0 for x >= 0 and pi for x < 0 (paper Section 2; zero
+ * is the non-negative GOOM with real part -inf).  Arrays of GOOMs use the interleaved
+ * complex layout (re, im): GOOM_C64 has float components, GOOM_C128 double components
+ * (paper Section 3).
+ *
+ * Conventions for every call
+ *   - C linkage, plain pointers and sizes; no exception crosses the boundary.
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library reads
+ *     inputs, writes outputs and the caller-provided workspace, and keeps none of them
+ *     after the enqueued work has finished.  It never allocates or frees device memory.
+ *   - Work is enqueued on the context's HIP stream and is asynchronous: results are
+ *     valid once the caller has synchronised that stream.  Inputs are never modified;
+ *     outputs and the workspace may not overlap inputs or each other.
+ *   - Matrices are row-major with the innermost index contiguous; a leading "batch"
+ *     index runs over independent problems (paper Section 3: functions broadcast over
+ *     preceding indices).  Complex data must be 16-byte aligned, real data aligned to
+ *     its element size, the workspace to 256 bytes.
+ *   - Return value: GOOM_OK or a negative goom_status.  goom_last_error(ctx) returns a
+ *     message for the last failure on that context (thread-local when ctx is NULL).
+ *     Arguments are validated on the host before anything is enqueued; a failed call
+ *     enqueues nothing.
+ *   - Only imaginary parts 0 and pi (of the component type) are ever written.  On input
+ *     any multiple of pi is accepted; the sign is the parity of round(im / pi).
+ *   - Non-finite log-magnitudes other than -inf (that is +inf and NaN) are outside the
+ *     contract of the product calls.
+ *
+ * Range of the product calls.  Inside a product the factors are exponentiated after a
+ * per-row shift of the left factor and a per-column shift of the right factor (paper
+ * Section 3.2, eq. 7), so within one row-by-column sum terms smaller than the largest
+ * possible term by more than the component format's range (about e^-87 for GOOM_C64,
+ * e^-708 for GOOM_C128) are dropped, as in the paper's own implementation.
+ * goom_lmme can be asked to repair such sums exactly (GOOM_LMME_EXACT).
+ */
+#ifndef GOOM_H
+#define GOOM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+#pragma GCC visibility push(default)
+
+#define GOOM_VERSION 100 /* major * 10000 + minor * 100 + patch */
+
+typedef struct goom_ctx goom_ctx;
+
+typedef enum goom_status {
+    GOOM_OK = 0,
+    GOOM_EINVAL = -1,       /* null pointer, non-positive size, bad flag, misalignment */
+    GOOM_EUNSUPPORTED = -2, /* valid request outside what this build implements */
+    GOOM_EWORKSPACE = -3,   /* workspace missing or smaller than *_workspace_bytes */
+    GOOM_EHIP = -4,         /* a HIP runtime call failed (message has the HIP error) */
+    GOOM_ENOMEM = -5        /* host allocation failed */
+} goom_status;
+
+typedef enum goom_dtype {
+    GOOM_C64 = 0, /* complex64: float log-magnitude, float phase */
+    GOOM_C128 = 1 /* complex128: double log-magnitude, double phase */
+} goom_dtype;
+
+/* largest matrix dimension the product calls accept */
+#define GOOM_MAX_DIM 128
+
+/* flags of goom_to_goom: how log 0 is written (paper Section 3.1, configurable real log) */
+#define GOOM_ZERO_NEG_INF 0u /* log 0 = -inf (default) */
+#define GOOM_ZERO_FLOOR 1u   /* log 0 = 2 log(smallest normal): finite, exponentiates to 0 */
+
+/* flags of goom_lmme */
+#define GOOM_LMME_FAST 0u  /* scaled real product only (paper Section 3.2, eq. 7) */
+#define GOOM_LMME_EXACT 1u /* additionally recompute, by a signed log-sum-exp over the
+                              terms (eq. 6), every output whose scaled product lost
+                              terms to underflow */
+
+/* ---- context ------------------------------------------------------------------- */
+
+int goom_version(void);
+
+/* Create a context bound to HIP device `device` and to `stream` (a hipStream_t passed as
+ * void*; NULL = the device's default stream).  The stream stays owned by the caller.
+ * Fails with GOOM_EHIP when the device cannot be used. */
+int goom_create(goom_ctx **ctx, int device, void *stream);
+int goom_destroy(goom_ctx *ctx);
+int goom_set_stream(goom_ctx *ctx, void *stream);
+const char *goom_last_error(const goom_ctx *ctx);
+const char *goom_status_name(int status);
+
+/* ---- codecs (paper Section 3.1) -------------------------------------------------- */
+
+/* Real floats -> GOOMs: y[i] = (log|x[i]|, x[i] < 0 ? pi : 0).  x: n floats (GOOM_C64)
+ * or n doubles (GOOM_C128); y: n complex.  The logarithm is rounded once from a
+ * higher-precision evaluation.  +-0 -> (-inf, 0) or (floor, 0) per `flags`;
+ * NaN -> (NaN, 0); +-inf -> (+inf, 0 or pi).  n = 0 is a no-op. */
+int goom_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, uint32_t flags);
+
+/* GOOMs -> real floats: x[i] = +-exp(Re y[i]), the real part of the complex exponential
+ * (paper Section 3.1, eq. 4); overflow gives +-inf, underflow +-0. */
+int goom_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype);
+
+/* ---- LMME (paper Section 3.2) ---------------------------------------------------- */
+
+/* C[b] = LMME(A[b], B[b]) = log(exp(A[b]) exp(B[b])) for b < batch.
+ * A: [batch, n, d], B: [batch, d, m], C: [batch, n, m] GOOMs; 1 <= n, d, m <= GOOM_MAX_DIM.
+ * Computed as the paper's scaled real product on the matrix cores (eq. 7) with row
+ * shifts max_j Re A_ij and column shifts max_j Re B_jk (0 for an all-zero row/column).
+ * A sum that is exactly zero gives (-inf, 0).  flags: GOOM_LMME_FAST or GOOM_LMME_EXACT.
+ * workspace: goom_lmme_workspace_bytes(...) bytes (may be 0 -> NULL allowed). */
+int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batch, int n, int d,
+              int m, int dtype, uint32_t flags, void *workspace, size_t workspace_bytes);
+size_t goom_lmme_workspace_bytes(int64_t batch, int n, int d, int m, int dtype, uint32_t flags);
+
+/* ---- prefix scan of a chain of matrix products (paper Section 4.1; Section 4.2.2) -- */
+
+typedef struct goom_scan_opts {
+    int64_t chunk_len; /* matrices per chunk of the three-phase scan; 0 = library default */
+    uint32_t flags;    /* reserved, must be 0 */
+} goom_scan_opts;
+
+/* Inclusive prefix products, newer factor on the left (paper eq. 9):
+ *     P[b, 0] = LMME(M[b, 0], init[b])      (or M[b, 0] itself when init is NULL)
+ *     P[b, t] = LMME(M[b, t], P[b, t-1])
+ * M: [batch, T, d, d]; init: NULL or [batch, d, m] (m != d allowed, e.g. a vector u_0,
+ * m = 1); P: [batch, T, d, m] (m = d when init is NULL).  opts may be NULL.
+ * The chain is cut into chunks: phase 1 multiplies each chunk down to one matrix,
+ * phase 2 scans those chunk products, phase 3 re-walks every chunk from its incoming
+ * prefix and writes all outputs.  Between steps the running product is kept as real
+ * mantissas with a power-of-two exponent per column, so log-magnitudes are rounded to
+ * the component type only when an output is stored.
+ * workspace: goom_scan_workspace_bytes(...) bytes. */
+int goom_scan(goom_ctx *ctx, const void *M, const void *init, void *P, int64_t T, int d, int m,
+              int64_t batch, int dtype, const goom_scan_opts *opts, void *workspace,
+              size_t workspace_bytes);
+size_t goom_scan_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype,
+                                 const goom_scan_opts *opts);
+
+/* Only the last prefix: P_final[b] = P[b, T-1] of goom_scan ([batch, d, m]); phases 1 and
+ * 2 only, so the input is read once (the product inside the paper's largest-exponent
+ * formula, Section 4.2.2, eq. 17). */
+int goom_reduce(goom_ctx *ctx, const void *M, const void *init, void *P_final, int64_t T, int d,
+                int m, int64_t batch, int dtype, const goom_scan_opts *opts, void *workspace,
+                size_t workspace_bytes);
+size_t goom_reduce_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype,
+                                   const goom_scan_opts *opts);
+
+/* ---- selectively reset scan and Lyapunov spectrum (paper Section 5; Section 4.2.1) - */
+
+#define GOOM_RESET_ALWAYS 1     /* reset at every examined state */
+#define GOOM_RESET_COLINEAR 0   /* reset when any two columns have |cosine| > threshold */
+#define GOOM_RESET_NEVER (-1)   /* plain scan */
+
+typedef struct goom_reset_opts {
+    int64_t chunk_len;    /* states are examined every chunk_len steps (t = chunk_len,
+                             2 chunk_len, ...); 0 = library default (64) */
+    int32_t policy;       /* GOOM_RESET_* */
+    float cos_threshold;  /* used by GOOM_RESET_COLINEAR */
+} goom_reset_opts;
+
+/* X[b, t] = J[b, t] X[b, t-1], t = 0..T-1 in array terms, X[b, -1] = S0[b] (NULL =
+ * identity), over GOOMs, with the selective-resetting method applied to the true
+ * prefix states at chunk boundaries: a selected state is replaced by the orthonormal
+ * factor Q of its column-normalised real form (paper Section 4.2.1 (a)), and all later
+ * states continue from Q.
+ * J: [batch, T, d, d]; S0: NULL or [batch, d, d]; states: [batch, T, d, d] (the state
+ * after any reset at that step); reset_flags: NULL or [batch, T] bytes (1 where a reset
+ * happened); growth: NULL or [batch, d] doubles: per column, the sum over resets of
+ * log R_kk + log(column norm), plus the same for the final state, i.e. the total
+ * log-growth of the k-th orthogonalised direction.
+ * workspace: goom_scan_reset_workspace_bytes(...) bytes. */
+int goom_scan_reset(goom_ctx *ctx, const void *J, const void *S0, void *states,
+                    uint8_t *reset_flags, double *growth, int64_t T, int d, int64_t batch,
+                    int dtype, const goom_reset_opts *opts, void *workspace,
+                    size_t workspace_bytes);
+size_t goom_scan_reset_workspace_bytes(int64_t T, int d, int64_t batch, int dtype,
+                                       const goom_reset_opts *opts);
+
+/* Lyapunov spectrum from the reset scan: lambda[b, k] = growth[b, k] / (dt T)
+ * (paper eq. 12 with the triangular factors accumulated at the resets).  states is
+ * optional here (NULL = do not store them).  lambda: [batch, d] doubles. */
+int goom_lyapunov_spectrum(goom_ctx *ctx, const void *J, const void *S0, void *states,
+                           double *lambda, int64_t T, int d, double dt, int64_t batch, int dtype,
+                           const goom_reset_opts *opts, void *workspace, size_t workspace_bytes);
+
+/* ---- linear recurrence with bias (paper Section 4.3, eqs. 18 and 20) ---------------- */
+
+/* h[b, t] = A[b, t] h[b, t-1] + bias[b, t], h[b, -1] = h0[b] (NULL = zero vector), over
+ * GOOMs.  A: [batch, T, d, d]; bias: [batch, T, d]; h0: NULL or [batch, d];
+ * H: [batch, T, d].  Scanned as products of the augmented matrices [A | bias; 0 | 1]
+ * whose last row is kept implicit.
+ * workspace: goom_affine_scan_workspace_bytes(...) bytes. */
+int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H,
+                     int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts,
+                     void *workspace, size_t workspace_bytes);
+size_t goom_affine_scan_workspace_bytes(int64_t T, int d, int64_t batch, int dtype,
+                                        const goom_scan_opts *opts);
+
+#pragma GCC visibility pop
+#ifdef __cplusplus
+}
+#endif
+#endif /* GOOM_H */

@@ -1,0 +1,286 @@
+"""ctypes binding over libgoom's C ABI (``include/goom.h``), same names as the C calls.
+
+Marshalling only: every step of the computation runs in the HIP kernels.  PyTorch is
+used for device memory and streams.  Tensors must be contiguous CUDA (ROCm) tensors on
+the context's device; complex64 / complex128 tensors carry GOOMs (real = log-magnitude,
+imag = 0 or pi).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgoom.so")
+_lib = None
+
+C64, C128 = 0, 1
+ZERO_NEG_INF, ZERO_FLOOR = 0, 1
+LMME_FAST, LMME_EXACT = 0, 1
+RESET_ALWAYS, RESET_COLINEAR, RESET_NEVER = 1, 0, -1
+
+EXPORTS = [
+    "goom_version", "goom_create", "goom_destroy", "goom_set_stream", "goom_last_error",
+    "goom_status_name", "goom_to_goom", "goom_from_goom", "goom_lmme", "goom_lmme_workspace_bytes",
+    "goom_scan", "goom_scan_workspace_bytes", "goom_reduce", "goom_reduce_workspace_bytes",
+    "goom_scan_reset", "goom_scan_reset_workspace_bytes", "goom_lyapunov_spectrum",
+    "goom_affine_scan", "goom_affine_scan_workspace_bytes",
+]
+
+
+class GoomError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{status_name(status)}: {message}")
+        self.status = status
+
+
+class ScanOpts(C.Structure):
+    _fields_ = [("chunk_len", C.c_int64), ("flags", C.c_uint32)]
+
+
+class ResetOpts(C.Structure):
+    _fields_ = [("chunk_len", C.c_int64), ("policy", C.c_int32), ("cos_threshold", C.c_float)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libgoom.so.  It must have been built (``python -m paper_2510_03426_amd.build`` or
+    ``__graft_entry__.build()``); there is no fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise GoomErrorNoLib()
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, i64, u32, sz = C.c_void_p, C.c_int, C.c_int64, C.c_uint32, C.c_size_t
+    lib.goom_version.restype = i32
+    lib.goom_create.argtypes = [C.POINTER(vp), i32, vp]
+    lib.goom_destroy.argtypes = [vp]
+    lib.goom_set_stream.argtypes = [vp, vp]
+    lib.goom_last_error.argtypes = [vp]
+    lib.goom_last_error.restype = C.c_char_p
+    lib.goom_status_name.argtypes = [i32]
+    lib.goom_status_name.restype = C.c_char_p
+    lib.goom_to_goom.argtypes = [vp, vp, vp, sz, i32, u32]
+    lib.goom_from_goom.argtypes = [vp, vp, vp, sz, i32]
+    lib.goom_lmme.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i32, u32, vp, sz]
+    lib.goom_lmme_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, u32]
+    lib.goom_lmme_workspace_bytes.restype = sz
+    po = C.POINTER(ScanOpts)
+    lib.goom_scan.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i32, po, vp, sz]
+    lib.goom_scan_workspace_bytes.argtypes = [i64, i32, i32, i64, i32, po]
+    lib.goom_scan_workspace_bytes.restype = sz
+    lib.goom_reduce.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i32, po, vp, sz]
+    lib.goom_reduce_workspace_bytes.argtypes = [i64, i32, i32, i64, i32, po]
+    lib.goom_reduce_workspace_bytes.restype = sz
+    pr = C.POINTER(ResetOpts)
+    lib.goom_scan_reset.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, pr, vp, sz]
+    lib.goom_scan_reset_workspace_bytes.argtypes = [i64, i32, i64, i32, pr]
+    lib.goom_scan_reset_workspace_bytes.restype = sz
+    lib.goom_lyapunov_spectrum.argtypes = [vp, vp, vp, vp, vp, i64, i32, C.c_double, i64, i32, pr, vp, sz]
+    lib.goom_affine_scan.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
+    lib.goom_affine_scan_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
+    lib.goom_affine_scan_workspace_bytes.restype = sz
+    _lib = lib
+    return lib
+
+
+class GoomErrorNoLib(RuntimeError):
+    def __init__(self):
+        super().__init__(f"{_LIB_PATH} is not built; run __graft_entry__.build() (hipcc, gfx950). "
+                         "There is no CPU fallback.")
+
+
+def status_name(status: int) -> str:
+    return load_library().goom_status_name(status).decode()
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype in (torch.complex64, torch.float32):
+        return C64
+    if t.dtype in (torch.complex128, torch.float64):
+        return C128
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("libgoom takes contiguous device tensors")
+    return C.c_void_p(t.data_ptr())
+
+
+class Goom:
+    """A libgoom context on one device, bound to torch's current stream at creation (or
+    to ``stream``).  Methods mirror the C entry points and allocate outputs/workspaces
+    with torch."""
+
+    def __init__(self, device: int = 0, stream=None):
+        import torch
+        self.torch = torch
+        self.lib = load_library()
+        self.device = torch.device("cuda", device)
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device)
+        self._stream = stream
+        self._ctx = C.c_void_p()
+        st = self.lib.goom_create(C.byref(self._ctx), device, C.c_void_p(stream.cuda_stream))
+        if st != 0:
+            raise GoomError(st, self.lib.goom_last_error(None).decode())
+        self._ws = None
+
+    def close(self):
+        if self._ctx:
+            self.lib.goom_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st):
+        if st != 0:
+            raise GoomError(st, self.lib.goom_last_error(self._ctx).decode())
+
+    def set_stream(self, stream):
+        self._stream = stream
+        self._check(self.lib.goom_set_stream(self._ctx, C.c_void_p(stream.cuda_stream)))
+
+    def workspace(self, nbytes: int):
+        """A cached 256-byte aligned scratch tensor of at least nbytes (None for 0)."""
+        if nbytes == 0:
+            return None, 0
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = self.torch.empty(nbytes, dtype=self.torch.uint8, device=self.device)
+        return self._ws, self._ws.numel()
+
+    # ---- codecs
+    def to_goom(self, x, flags: int = ZERO_NEG_INF, out=None):
+        torch = self.torch
+        code = _dtype_code(x)
+        if out is None:
+            out = torch.empty(x.shape, dtype=torch.complex64 if code == C64 else torch.complex128, device=x.device)
+        self._check(self.lib.goom_to_goom(self._ctx, _ptr(x), _ptr(out), x.numel(), code, flags))
+        return out
+
+    def from_goom(self, y, out=None):
+        torch = self.torch
+        code = _dtype_code(y)
+        if out is None:
+            out = torch.empty(y.shape, dtype=torch.float32 if code == C64 else torch.float64, device=y.device)
+        self._check(self.lib.goom_from_goom(self._ctx, _ptr(y), _ptr(out), y.numel(), code))
+        return out
+
+    # ---- LMME
+    def lmme(self, a, b, flags: int = LMME_FAST, out=None):
+        torch = self.torch
+        code = _dtype_code(a)
+        n, d = a.shape[-2:]
+        d2, m = b.shape[-2:]
+        assert d == d2 and a.shape[:-2] == b.shape[:-2] and a.dtype == b.dtype
+        batch = 1
+        for s in a.shape[:-2]:
+            batch *= s
+        if out is None:
+            out = torch.empty(a.shape[:-2] + (n, m), dtype=a.dtype, device=a.device)
+        ws, wsn = self.workspace(self.lib.goom_lmme_workspace_bytes(batch, n, d, m, code, flags))
+        self._check(self.lib.goom_lmme(self._ctx, _ptr(a), _ptr(b), _ptr(out), batch, n, d, m, code, flags,
+                                       _ptr(ws), wsn))
+        return out
+
+    # ---- scans
+    def _scan_shapes(self, mats, init):
+        T, d, d2 = mats.shape[-3:]
+        assert d == d2
+        lead = mats.shape[:-3]
+        batch = 1
+        for s in lead:
+            batch *= s
+        if init is not None:
+            assert init.shape[:-2] == lead and init.shape[-2] == d and init.dtype == mats.dtype
+            m = init.shape[-1]
+        else:
+            m = d
+        return lead, batch, T, d, m
+
+    def scan(self, mats, init=None, chunk_len: int = 0, out=None):
+        torch = self.torch
+        code = _dtype_code(mats)
+        lead, batch, T, d, m = self._scan_shapes(mats, init)
+        opts = ScanOpts(chunk_len, 0)
+        if out is None:
+            out = torch.empty(lead + (T, d, m), dtype=mats.dtype, device=mats.device)
+        ws, wsn = self.workspace(self.lib.goom_scan_workspace_bytes(T, d, m, batch, code, C.byref(opts)))
+        self._check(self.lib.goom_scan(self._ctx, _ptr(mats), _ptr(init), _ptr(out), T, d, m, batch, code,
+                                       C.byref(opts), _ptr(ws), wsn))
+        return out
+
+    def reduce(self, mats, init=None, chunk_len: int = 0, out=None):
+        torch = self.torch
+        code = _dtype_code(mats)
+        lead, batch, T, d, m = self._scan_shapes(mats, init)
+        opts = ScanOpts(chunk_len, 0)
+        if out is None:
+            out = torch.empty(lead + (d, m), dtype=mats.dtype, device=mats.device)
+        ws, wsn = self.workspace(self.lib.goom_reduce_workspace_bytes(T, d, m, batch, code, C.byref(opts)))
+        self._check(self.lib.goom_reduce(self._ctx, _ptr(mats), _ptr(init), _ptr(out), T, d, m, batch, code,
+                                         C.byref(opts), _ptr(ws), wsn))
+        return out
+
+    def affine_scan(self, a, bias, h0=None, chunk_len: int = 0, out=None):
+        torch = self.torch
+        code = _dtype_code(a)
+        T, d = bias.shape[-2:]
+        lead = bias.shape[:-2]
+        assert a.shape == lead + (T, d, d) and a.dtype == bias.dtype
+        batch = 1
+        for s in lead:
+            batch *= s
+        opts = ScanOpts(chunk_len, 0)
+        if out is None:
+            out = torch.empty(lead + (T, d), dtype=a.dtype, device=a.device)
+        ws, wsn = self.workspace(self.lib.goom_affine_scan_workspace_bytes(T, d, batch, code, C.byref(opts)))
+        self._check(self.lib.goom_affine_scan(self._ctx, _ptr(a), _ptr(bias), _ptr(h0), _ptr(out), T, d, batch,
+                                              code, C.byref(opts), _ptr(ws), wsn))
+        return out
+
+    def scan_reset(self, jac, s0=None, chunk_len: int = 0, policy: int = RESET_ALWAYS,
+                   cos_threshold: float = 0.99, want_states: bool = True):
+        torch = self.torch
+        code = _dtype_code(jac)
+        T, d, _ = jac.shape[-3:]
+        lead = jac.shape[:-3]
+        batch = 1
+        for s in lead:
+            batch *= s
+        opts = ResetOpts(chunk_len, policy, cos_threshold)
+        states = torch.empty(lead + (T, d, d), dtype=jac.dtype, device=jac.device)
+        flags = torch.zeros(lead + (T,), dtype=torch.uint8, device=jac.device)
+        growth = torch.zeros(lead + (d,), dtype=torch.float64, device=jac.device)
+        ws, wsn = self.workspace(self.lib.goom_scan_reset_workspace_bytes(T, d, batch, code, C.byref(opts)))
+        self._check(self.lib.goom_scan_reset(self._ctx, _ptr(jac), _ptr(s0), _ptr(states), _ptr(flags), _ptr(growth),
+                                             T, d, batch, code, C.byref(opts), _ptr(ws), wsn))
+        return states, flags, growth
+
+    def lyapunov_spectrum(self, jac, dt: float, s0=None, chunk_len: int = 0, policy: int = RESET_ALWAYS,
+                          cos_threshold: float = 0.99):
+        torch = self.torch
+        code = _dtype_code(jac)
+        T, d, _ = jac.shape[-3:]
+        lead = jac.shape[:-3]
+        batch = 1
+        for s in lead:
+            batch *= s
+        opts = ResetOpts(chunk_len, policy, cos_threshold)
+        lam = torch.zeros(lead + (d,), dtype=torch.float64, device=jac.device)
+        ws, wsn = self.workspace(self.lib.goom_scan_reset_workspace_bytes(T, d, batch, code, C.byref(opts)))
+        self._check(self.lib.goom_lyapunov_spectrum(self._ctx, _ptr(jac), _ptr(s0), None, _ptr(lam), T, d, dt, batch,
+                                                    code, C.byref(opts), _ptr(ws), wsn))
+        return lam

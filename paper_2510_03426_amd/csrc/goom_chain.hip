@@ -1,0 +1,70 @@
+// Host side of the chain kernel: picks the instantiation and fills the kernel arguments.
+#include "goom_chain_kernel.h"
+
+using goom_chain::ChainArgs;
+
+namespace goom {
+
+FactLayout fact_layout(int dp, int m, int dtype)
+{
+    FactLayout f;
+    f.rows_padded = dp;
+    f.cols_padded = (m + 15) / 16 * 16;
+    size_t comp = dtype == GOOM_C64 ? 4 : 8;
+    f.mant_bytes = (size_t)f.rows_padded * f.cols_padded * comp;
+    f.stride = align_up(f.mant_bytes + (size_t)f.cols_padded * sizeof(double), 256);
+    return f;
+}
+
+int padded_dim(int d) { return d <= 16 ? 16 : d <= 32 ? 32 : d <= 64 ? 64 : 128; }
+
+// Waves per workgroup: one per 16-column slab of the state, rounded up to a width the
+// kernel is instantiated for.
+static int pick_waves(int dp, int nslabs)
+{
+    const int kt = dp / 16;
+    if (nslabs <= 1) return 1;
+    if (nslabs <= kt) return kt;
+    if (nslabs == kt + 1 && dp != 128) return kt + 1;
+    return -1;
+}
+
+int launch_chain(goom_ctx *ctx, const ChainLaunch &l)
+{
+    const int dp = padded_dim(l.n > l.d ? l.n : l.d);
+    const int nslabs = (l.m + 15) / 16;
+    const int nw = pick_waves(dp, nslabs);
+    if (nw < 0) return fail(ctx, GOOM_EUNSUPPORTED, "state of %d columns with d = %d is not supported", l.m, l.d);
+    ChainArgs a;
+    a.left = static_cast<const unsigned char *>(l.left);
+    a.left_batch_stride = l.left_batch_stride;
+    a.left_step_stride = l.left_step_stride;
+    a.steps = l.steps;
+    a.chunk_len = l.chunk_len;
+    a.chunks_per_item = (l.steps + l.chunk_len - 1) / l.chunk_len;
+    a.chunks_launched = l.chunks_launched;
+    a.n = l.n;
+    a.d = l.d;
+    a.m = l.m;
+    a.nslabs = nslabs;
+    a.init_mode = l.init_mode;
+    a.init = static_cast<const unsigned char *>(l.init);
+    a.init_stride = l.init_stride;
+    a.out_goom = static_cast<unsigned char *>(l.out_goom);
+    a.out_goom_last_only = l.out_goom_last_only;
+    a.out_fact_steps = static_cast<unsigned char *>(l.out_fact_steps);
+    a.out_fact_final = static_cast<unsigned char *>(l.out_fact_final);
+    a.final_common_exponent = l.final_common_exponent;
+    a.fact_stride = l.fact_stride;
+    a.fact_cols = l.fact_cols;
+    a.left_fact_cols = l.left_fact_cols;
+    a.bias_mode = l.bias_mode;
+    a.bias_col = l.bias_col;
+    a.bias = static_cast<const unsigned char *>(l.bias);
+    const long long grid = l.batch * l.chunks_launched;
+    if (l.dtype == GOOM_C64)
+        return l.left_fact ? goom_chain::dispatch_f32_fact(ctx, a, dp, nw, grid) : goom_chain::dispatch_f32_goom(ctx, a, dp, nw, grid);
+    return l.left_fact ? goom_chain::dispatch_f64_fact(ctx, a, dp, nw, grid) : goom_chain::dispatch_f64_goom(ctx, a, dp, nw, grid);
+}
+
+} // namespace goom

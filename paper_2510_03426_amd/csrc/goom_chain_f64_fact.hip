@@ -1,0 +1,9 @@
+// chain kernel instantiations: double components, left factors factored
+#include "goom_chain_kernel.h"
+
+namespace goom_chain {
+int dispatch_f64_fact(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid)
+{
+    return dispatch<double, 1>(ctx, args, dp, nw, grid);
+}
+} // namespace goom_chain

@@ -1,0 +1,539 @@
+// Chain kernel: walks a sequence of left factors M_1, M_2, ... and keeps the running
+// product S <- M_t S on chip.  It is the combine of the prefix scan (paper Section 4.1,
+// eq. 9: S'_t = LMME(A'_t, S'_{t-1})) and, with one step, LMME itself (Section 3.2).
+//
+// Each step is the paper's scaled real product (Section 3.2, eq. 7) with two changes that
+// keep what the identity of eq. 10 allows:
+//   * all shifts are whole powers of two, so scaling never rounds;
+//   * the running product is not turned back into logarithms between steps.  It stays a
+//     matrix of real mantissas W with one exponent per column, S[:, k] = W[:, k] 2^e_k
+//     (left multiplication acts on every column independently, so a per-column scale
+//     commutes with the product).  Logarithms are taken only for values that are stored.
+//
+// Work decomposition (wave64, v_mfma_*_16x16x4): a workgroup owns one chain; wave w owns
+// the 16-column slab w of the state for all rows.  The 16x16 accumulator tile of the
+// matrix instruction puts four rows of column lane % 16 in one lane (rows 4g+v for float,
+// 4v+g for double; g = lane / 16, v = register), and the B operand wants one row per
+// lane group g of that column: so the accumulators of one step are, register for
+// register, the B operands of the next, with the contraction index visited in the
+// order the accumulator rows come in.  The left factor is exponentiated by all
+// waves into a padded LDS tile (double buffered), from which A operands are read as
+// 16-byte vectors.
+#pragma once
+#include "goom_internal.h"
+
+namespace goom_chain {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef double d4 __attribute__((ext_vector_type(4)));
+
+constexpr double kLog2e = 1.44269504088896340736;
+constexpr double kLn2 = 0.693147180559945309417;
+constexpr double kNegBig = -1.0e300; // stands for "log2 of zero" in exponent arithmetic
+
+struct ChainArgs {
+    const unsigned char *left;
+    long long left_batch_stride, left_step_stride;
+    long long steps, chunk_len, chunks_per_item, chunks_launched;
+    int n, d, m, nslabs; // left factors are n x d, the state is d x m, outputs are n x m
+    int init_mode;
+    const unsigned char *init;
+    long long init_stride;
+    unsigned char *out_goom;
+    int out_goom_last_only;
+    unsigned char *out_fact_steps;
+    unsigned char *out_fact_final;
+    int final_common_exponent;
+    long long fact_stride;
+    int fact_cols;      // padded columns of factored states written / read
+    int left_fact_cols; // padded columns of factored left factors
+    int bias_mode; // 0 none, 1 GOOM vectors [batch, steps, d], 2 column d of the factored left factor
+    int bias_col;  // state column that receives the bias
+    const unsigned char *bias;
+};
+
+template <typename R> struct Comp;
+template <> struct Comp<float> {
+    typedef f4 vec4;
+    static constexpr int kPad = 4; // LDS row padding in elements
+    __device__ static float pi() { return 3.14159274101257324219f; }
+    __device__ static f4 mfma(float a, float b, f4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+    __device__ static float exp2_frac(float f) { return __builtin_amdgcn_exp2f(f); }
+    __device__ static float log2_abs(float x) { return ::log2f(__builtin_fabsf(x)); }
+    __device__ static float ldexp_(float x, int e) { return __builtin_ldexpf(x, e); }
+    __device__ static int frexp_exp(float x) { int e; (void)__builtin_frexpf(x, &e); return e; }
+    __device__ static float inv_pi() { return 0.318309886183790671538f; }
+    __device__ static float abs_(float x) { return __builtin_fabsf(x); }
+    // accumulator register v of lane group g holds row 4 g + v of the 16 x 16 tile
+    __device__ static int row_of(int g, int v) { return 4 * g + v; }
+    // position of logical index j inside LDS rows / the row-shift array
+    __device__ static int phys(int j) { return j; }
+};
+template <> struct Comp<double> {
+    typedef d4 vec4;
+    static constexpr int kPad = 2;
+    __device__ static double pi() { return 3.14159265358979311600; }
+    __device__ static d4 mfma(double a, double b, d4 c) { return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0); }
+    __device__ static double exp2_frac(double f) { return ::exp2(f); }
+    __device__ static double log2_abs(double x) { return ::log2(__builtin_fabs(x)); }
+    __device__ static double ldexp_(double x, int e) { return __builtin_ldexp(x, e); }
+    __device__ static int frexp_exp(double x) { int e; (void)__builtin_frexp(x, &e); return e; }
+    __device__ static double inv_pi() { return 0.318309886183790671538; }
+    __device__ static double abs_(double x) { return __builtin_fabs(x); }
+    // the double-precision instruction interleaves rows: register v of lane group g holds row 4 v + g
+    __device__ static int row_of(int g, int v) { return 4 * v + g; }
+    // ... so contraction index 16 kt + 4 v + g is stored at position 16 kt + 4 g + v, which
+    // keeps the four values a lane needs contiguous
+    __device__ static int phys(int j) { return (j & ~15) | ((j & 3) << 2) | ((j >> 2) & 3); }
+};
+
+// 2^(t) for a double exponent t <= ~0 (t = -inf allowed): split into integer and
+// fraction in double so the fraction is exact, then one hardware exp2 and an ldexp.
+template <typename R> __device__ inline R exp2_shifted(double t)
+{
+    t = t > -4000.0 ? t : -4000.0; // also maps -inf and NaN to "underflows to zero"
+    t = t < 4000.0 ? t : 4000.0;
+    double k = __builtin_rint(t);
+    R f = (R)(t - k);
+    return Comp<R>::ldexp_(Comp<R>::exp2_frac(f), (int)k);
+}
+
+// sign carried by the imaginary part: negative iff im is an odd multiple of pi
+template <typename R> __device__ inline bool is_negative(R im)
+{
+    int k = (int)__builtin_rint((double)(im * Comp<R>::inv_pi()));
+    return (k & 1) != 0;
+}
+
+template <typename R> __device__ inline R wave_xor_max(R v, int mask)
+{
+    R o = __shfl_xor(v, mask, 64);
+    return o > v ? o : v;
+}
+
+__device__ inline double shfl_xor_double(double v, int mask) { return __shfl_xor(v, mask, 64); }
+
+// One item of the producer: two horizontally adjacent elements of the left factor.
+template <typename R> struct Item {
+    R re0, im0, re1, im1;
+};
+
+template <typename R, int DP, int NW, int LEFT_FACT>
+__global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
+{
+    constexpr int KT = DP / 16;
+    constexpr int LPR = DP / 2; // producer lanes per row
+    constexpr int NT = NW * 64;
+    constexpr int LDA = DP + Comp<R>::kPad;
+    constexpr int NITEMS = DP * LPR;
+    constexpr int Q = (NITEMS + NT - 1) / NT; // items per thread
+    constexpr int QB = Q < 8 ? Q : 8;         // items loaded ahead per batch
+    typedef typename Comp<R>::vec4 vec4;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr size_t kTileBytes = (size_t)DP * LDA * sizeof(R);
+    constexpr size_t kBufBytes = kTileBytes + (size_t)DP * sizeof(double);
+    constexpr int NBUF = (2 * kBufBytes + 64 <= 160 * 1024) ? 2 : 1; // double buffer when it fits in LDS
+    // buffer b: tile at smem + b * kBufBytes, row shifts (double) after the tile
+    auto tile_of = [&](int b) { return reinterpret_cast<R *>(smem + (size_t)b * kBufBytes); };
+    auto nsh_of = [&](int b) { return reinterpret_cast<double *>(smem + (size_t)b * kBufBytes + kTileBytes); };
+    double *wave_red = reinterpret_cast<double *>(smem + NBUF * kBufBytes); // NW doubles
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int g = lane >> 4;
+    const int c = lane & 15;
+    const int n_rows = a.n, d = a.d, m = a.m;
+    const int col = wave * 16 + c;
+    const bool slab_active = wave < a.nslabs;
+
+    const long long chain = blockIdx.x;
+    const long long item = chain / a.chunks_launched;
+    const long long chunk = chain % a.chunks_launched;
+    const long long t0 = chunk * a.chunk_len;
+    long long len = a.steps - t0;
+    if (len > a.chunk_len) len = a.chunk_len;
+    const long long chain_global = item * a.chunks_per_item + chunk; // index into per-chain arrays
+
+    const unsigned char *left0 = a.left + item * a.left_batch_stride + t0 * a.left_step_stride;
+
+    // ------------------------------------------------------------------ producer
+    // Exponentiate left factor number t into LDS buffer buf:
+    //   tile[i][j] = (+-) 2^(log2|A_ij| - n_i),  n_i = ceil(max_j log2|A_ij|)  (0 for a zero row)
+    // and record n_i.  Rows/columns beyond d are zero.
+    auto produce = [&](long long t, int buf) {
+        R *tile = tile_of(buf);
+        double *nsh = nsh_of(buf);
+        const unsigned char *src = left0 + t * a.left_step_stride;
+#pragma unroll
+        for (int q0 = 0; q0 < Q; q0 += QB) {
+            Item<R> it[QB];
+            double common = 0.0;
+#pragma unroll
+            for (int q = 0; q < QB; ++q) {
+                int p = tid + (q0 + q) * NT;
+                int row = p / LPR, cp = p % LPR, cj = 2 * cp;
+                bool v0 = (p < NITEMS) && row < n_rows && cj < d;
+                bool v1 = v0 && (cj + 1 < d);
+                if (LEFT_FACT) {
+                    // factored left factor: mantissas [DP][fact_cols], all columns on one exponent
+                    const R *mp = reinterpret_cast<const R *>(src) + (size_t)row * a.left_fact_cols + cj;
+                    it[q].re0 = v0 ? mp[0] : (R)0;
+                    it[q].re1 = v1 ? mp[1] : (R)0;
+                    it[q].im0 = it[q].im1 = (R)0;
+                } else {
+                    const R *gp = reinterpret_cast<const R *>(src) + ((size_t)row * d + cj) * 2;
+                    R ninf = -__builtin_huge_val();
+                    if (v1 && (d % 2 == 0)) {
+                        if (sizeof(R) == 4) {
+                            f4 w = *reinterpret_cast<const f4 *>(gp);
+                            it[q].re0 = w[0]; it[q].im0 = w[1]; it[q].re1 = w[2]; it[q].im1 = w[3];
+                        } else {
+                            it[q].re0 = gp[0]; it[q].im0 = gp[1]; it[q].re1 = gp[2]; it[q].im1 = gp[3];
+                        }
+                    } else {
+                        it[q].re0 = v0 ? gp[0] : ninf; it[q].im0 = v0 ? gp[1] : (R)0;
+                        it[q].re1 = v1 ? gp[2] : ninf; it[q].im1 = v1 ? gp[3] : (R)0;
+                    }
+                }
+            }
+            if (LEFT_FACT) {
+                const double *ex = reinterpret_cast<const double *>(src + (size_t)DP * a.left_fact_cols * sizeof(R));
+                common = ex[0];
+            }
+#pragma unroll
+            for (int q = 0; q < QB; ++q) {
+                int p = tid + (q0 + q) * NT;
+                int row = p / LPR, cp = p % LPR, cj = 2 * cp;
+                R x0, x1;
+                double n;
+                if (LEFT_FACT) {
+                    R a0 = Comp<R>::abs_(it[q].re0), a1 = Comp<R>::abs_(it[q].re1);
+                    R r = a0 > a1 ? a0 : a1;
+#pragma unroll
+                    for (int s = 1; s < LPR; s <<= 1) r = wave_xor_max<R>(r, s);
+                    int e = (r > (R)0 && r < (R)__builtin_huge_val()) ? Comp<R>::frexp_exp(r) : 0;
+                    x0 = Comp<R>::ldexp_(it[q].re0, -e);
+                    x1 = Comp<R>::ldexp_(it[q].re1, -e);
+                    n = (double)e + common;
+                } else {
+                    R r = it[q].re0 > it[q].re1 ? it[q].re0 : it[q].re1;
+#pragma unroll
+                    for (int s = 1; s < LPR; s <<= 1) r = wave_xor_max<R>(r, s);
+                    n = (r > -(R)__builtin_huge_val()) ? __builtin_ceil((double)r * kLog2e) : 0.0;
+                    x0 = exp2_shifted<R>(__builtin_fma((double)it[q].re0, kLog2e, -n));
+                    x1 = exp2_shifted<R>(__builtin_fma((double)it[q].re1, kLog2e, -n));
+                    if (is_negative<R>(it[q].im0)) x0 = -x0;
+                    if (is_negative<R>(it[q].im1)) x1 = -x1;
+                }
+                if (p < NITEMS) {
+                    tile[row * LDA + Comp<R>::phys(cj)] = x0;
+                    tile[row * LDA + Comp<R>::phys(cj + 1)] = x1;
+                    if (cp == 0) nsh[Comp<R>::phys(row)] = n;
+                }
+            }
+        }
+    };
+
+    // ------------------------------------------------------------------ initial state
+    R st[KT][4]; // st[kt][v] = W[16 kt + row_of(g, v)][col]
+    double ecol = 0.0;
+    const size_t fact_mant_bytes = (size_t)DP * a.fact_cols * sizeof(R);
+    if (a.init_mode == 0 || a.init_mode == 3) { // identity / zero
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * kt + Comp<R>::row_of(g, v);
+                st[kt][v] = (a.init_mode == 0 && row == col && row < d && col < m) ? (R)1 : (R)0;
+            }
+    } else if (a.init_mode == 1) {
+        const unsigned char *ip = a.init + chain_global * a.init_stride;
+        const R *mp = reinterpret_cast<const R *>(ip);
+        const double *ep = reinterpret_cast<const double *>(ip + fact_mant_bytes);
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                st[kt][v] = slab_active ? mp[(size_t)(16 * kt + Comp<R>::row_of(g, v)) * a.fact_cols + col] : (R)0;
+        ecol = slab_active ? ep[col] : 0.0;
+    } else {
+        // GOOM initial state [d, m]: column shift e = ceil(max_i log2|x_ik|), W = +-2^(log2|x| - e)
+        const R *gp = reinterpret_cast<const R *>(a.init + item * a.init_stride);
+        R re[KT][4], im[KT][4];
+        R cmax = -(R)__builtin_huge_val();
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                int row = 16 * kt + Comp<R>::row_of(g, v);
+                bool ok = slab_active && row < d && col < m;
+                re[kt][v] = ok ? gp[((size_t)row * m + col) * 2] : -(R)__builtin_huge_val();
+                im[kt][v] = ok ? gp[((size_t)row * m + col) * 2 + 1] : (R)0;
+                cmax = re[kt][v] > cmax ? re[kt][v] : cmax;
+            }
+        cmax = wave_xor_max<R>(cmax, 16);
+        cmax = wave_xor_max<R>(cmax, 32);
+        ecol = (cmax > -(R)__builtin_huge_val()) ? __builtin_ceil((double)cmax * kLog2e) : 0.0;
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                R x = exp2_shifted<R>(__builtin_fma((double)re[kt][v], kLog2e, -ecol));
+                st[kt][v] = is_negative<R>(im[kt][v]) ? -x : x;
+            }
+    }
+
+    auto store_fact = [&](unsigned char *dst, bool common_exponent) {
+        // dst: mantissas [DP][fact_cols] then exponents [fact_cols] (double)
+        R *mp = reinterpret_cast<R *>(dst);
+        double *ep = reinterpret_cast<double *>(dst + fact_mant_bytes);
+        double e_out = ecol;
+        int shift = 0;
+        if (common_exponent) {
+            // one exponent for the leading columns (< d when a bias column exists, all otherwise)
+            R cm = (R)0;
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    R av = Comp<R>::abs_(st[kt][v]);
+                    cm = av > cm ? av : cm;
+                }
+            cm = wave_xor_max<R>(cm, 16);
+            cm = wave_xor_max<R>(cm, 32);
+            const int ncommon = a.bias_mode ? d : m;
+            double ev = (slab_active && col < ncommon && cm > (R)0) ? ecol : kNegBig;
+#pragma unroll
+            for (int s = 1; s < 16; s <<= 1) {
+                double o = shfl_xor_double(ev, s);
+                ev = o > ev ? o : ev;
+            }
+            __syncthreads();
+            if (lane == 0) wave_red[wave] = ev;
+            __syncthreads();
+            double emax = kNegBig;
+            for (int w = 0; w < NW; ++w) emax = wave_red[w] > emax ? wave_red[w] : emax;
+            if (emax == kNegBig) emax = 0.0;
+            if (col < ncommon) {
+                double dsh = ecol - emax;
+                dsh = dsh > -4000.0 ? dsh : -4000.0;
+                shift = (cm > (R)0) ? (int)dsh : 0;
+                e_out = emax;
+            }
+        }
+        if (slab_active) {
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    mp[(size_t)(16 * kt + Comp<R>::row_of(g, v)) * a.fact_cols + col] = Comp<R>::ldexp_(st[kt][v], shift);
+            if (g == 0) ep[col] = e_out;
+        }
+    };
+
+    unsigned char *fact_steps = a.out_fact_steps ? a.out_fact_steps + (chain_global * (a.chunk_len + 1)) * a.fact_stride : nullptr;
+
+    if (len > 0) produce(0, 0);
+    __syncthreads();
+
+    for (long long t = 0; t < len; ++t) {
+        const int cur = NBUF == 2 ? (int)(t & 1) : 0;
+        const R *tile = tile_of(cur);
+        const double *nsh = nsh_of(cur);
+
+        if (fact_steps) store_fact(fact_steps + t * a.fact_stride, false);
+
+        // ------------------------------------------------------------ product on the matrix cores
+        vec4 acc[KT];
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) acc[mt] = vec4{0, 0, 0, 0};
+        if (slab_active) {
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt) {
+                vec4 av[KT];
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+                    av[mt] = *reinterpret_cast<const vec4 *>(&tile[(16 * mt + c) * LDA + 16 * kt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int mt = 0; mt < KT; ++mt) acc[mt] = Comp<R>::mfma(av[mt][v], st[kt][v], acc[mt]);
+            }
+        }
+
+        // ------------------------------------------------------------ epilogue
+        // acc[mt][v] is entry (i = 16 mt + 4 g + v, col) of the scaled product; the true
+        // value is acc * 2^(n_i + ecol).
+        //
+        // bias column (linear recurrence with bias): b_i, given as a GOOM or as a column
+        // of the factored left factor, is added to entry (i, bias_col) in the log2 domain.
+        const bool bias_lane = a.bias_mode != 0 && slab_active && col == a.bias_col;
+        auto bias_term = [&](int i, double &blog, bool &bneg) { // blog = log2|b_i| - ecol
+            blog = kNegBig;
+            bneg = false;
+            if (i >= n_rows) return;
+            if (a.bias_mode == 1) {
+                const R *bp = reinterpret_cast<const R *>(a.bias) + ((size_t)(item * a.steps + t0 + t) * n_rows + i) * 2;
+                R br = bp[0];
+                if (br > -(R)__builtin_huge_val()) blog = (double)br * kLog2e - ecol;
+                bneg = is_negative<R>(bp[1]);
+            } else {
+                const unsigned char *src = left0 + t * a.left_step_stride;
+                const R *mp = reinterpret_cast<const R *>(src);
+                const double *ex = reinterpret_cast<const double *>(src + (size_t)DP * a.left_fact_cols * sizeof(R));
+                R bv = mp[(size_t)i * a.left_fact_cols + d];
+                if (bv != (R)0) blog = (double)Comp<R>::log2_abs(bv) + ex[d] - ecol;
+                bneg = bv < (R)0;
+            }
+        };
+
+        // column reference: cm = max_i log2 of the entries in units of 2^ecol
+        double cm = kNegBig;
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) {
+            const d4 nv = *reinterpret_cast<const d4 *>(&nsh[16 * mt + 4 * g]);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                R x = acc[mt][v];
+                double lg = (x != (R)0) ? (double)Comp<R>::frexp_exp(x) + nv[v] : kNegBig;
+                cm = lg > cm ? lg : cm;
+            }
+        }
+        if (bias_lane) {
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    double blog;
+                    bool bneg;
+                    bias_term(16 * mt + Comp<R>::row_of(g, v), blog, bneg);
+                    cm = blog > cm ? blog : cm;
+                }
+        }
+        {
+            double o = shfl_xor_double(cm, 16);
+            cm = o > cm ? o : cm;
+            o = shfl_xor_double(cm, 32);
+            cm = o > cm ? o : cm;
+        }
+        if (bias_lane && cm > kNegBig) cm = __builtin_ceil(cm) + 2.0; // whole exponent, room for the sum of two terms
+        const bool col_nonzero = cm > kNegBig;
+
+        const bool want_out = a.out_goom && slab_active && col < m && (!a.out_goom_last_only || t == len - 1);
+        R *outp = nullptr;
+        if (want_out) {
+            long long o_idx = a.out_goom_last_only ? chain_global : (item * a.steps + t0 + t);
+            outp = reinterpret_cast<R *>(a.out_goom) + ((size_t)o_idx * n_rows * m) * 2;
+        }
+
+        if (!bias_lane) {
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                const d4 nv = *reinterpret_cast<const d4 *>(&nsh[16 * mt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int i = 16 * mt + Comp<R>::row_of(g, v);
+                    R x = acc[mt][v];
+                    if (want_out && i < n_rows) {
+                        // log-magnitude of the true value: (log2|x| + n_i + ecol) ln 2, rounded once
+                        R re = (x != (R)0) ? (R)(((double)Comp<R>::log2_abs(x) + nv[v] + ecol) * kLn2)
+                                           : -(R)__builtin_huge_val();
+                        R im = x < (R)0 ? Comp<R>::pi() : (R)0;
+                        R *o = outp + ((size_t)i * m + col) * 2;
+                        if (sizeof(R) == 4) {
+                            *reinterpret_cast<float2 *>(o) = float2{(float)re, (float)im};
+                        } else {
+                            *reinterpret_cast<double2 *>(o) = double2{(double)re, (double)im};
+                        }
+                    }
+                    double sh = nv[v] - cm;
+                    sh = sh > -4000.0 ? sh : -4000.0;
+                    st[mt][v] = col_nonzero ? Comp<R>::ldexp_(x, (int)sh) : (R)0;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                const d4 nv = *reinterpret_cast<const d4 *>(&nsh[16 * mt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int i = 16 * mt + Comp<R>::row_of(g, v);
+                    R x = acc[mt][v];
+                    double blog;
+                    bool bneg;
+                    bias_term(i, blog, bneg);
+                    // entry = x 2^(n_i - cm) + (+-) 2^(blog - cm), in units of 2^(ecol + cm)
+                    double sh = nv[v] - cm;
+                    sh = sh > -4000.0 ? sh : -4000.0;
+                    R xa = col_nonzero ? Comp<R>::ldexp_(x, (int)sh) : (R)0;
+                    R xb = (col_nonzero && blog > kNegBig) ? exp2_shifted<R>(blog - cm) : (R)0;
+                    R xs = xa + (bneg ? -xb : xb);
+                    if (want_out && i < n_rows) {
+                        R re = (xs != (R)0) ? (R)(((double)Comp<R>::log2_abs(xs) + cm + ecol) * kLn2)
+                                            : -(R)__builtin_huge_val();
+                        R im = xs < (R)0 ? Comp<R>::pi() : (R)0;
+                        R *o = outp + ((size_t)i * m + col) * 2;
+                        o[0] = re;
+                        o[1] = im;
+                    }
+                    st[mt][v] = xs;
+                }
+            }
+        }
+        if (col_nonzero) ecol += cm;
+
+        // ------------------------------------------------------------ next left factor
+        if (NBUF == 1) __syncthreads(); // every wave is done reading the only tile
+        if (t + 1 < len) produce(t + 1, NBUF == 2 ? (cur ^ 1) : 0);
+        __syncthreads();
+    }
+
+    if (fact_steps) store_fact(fact_steps + len * a.fact_stride, false);
+    if (a.out_fact_final) store_fact(a.out_fact_final + chain_global * a.fact_stride, a.final_common_exponent != 0);
+}
+
+template <typename R, int DP, int NW, int LEFT_FACT> int launch_one(goom_ctx *ctx, const ChainArgs &args, long long grid)
+{
+    constexpr int LDA = DP + Comp<R>::kPad;
+    const size_t buf = (size_t)DP * LDA * sizeof(R) + (size_t)DP * sizeof(double);
+    const int nbuf = (2 * buf + 64 <= 160 * 1024) ? 2 : 1;
+    size_t lds = nbuf * buf + 64;
+    auto kern = chain_kernel<R, DP, NW, LEFT_FACT>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return goom::check_hip(ctx, e, "hipFuncSetAttribute(chain_kernel)");
+    }
+    if (grid <= 0) return GOOM_OK;
+    if (grid > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many chains for one launch (%lld)", grid);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds, ctx->stream, args);
+    return goom::check_hip(ctx, hipGetLastError(), "launch chain_kernel");
+}
+
+template <typename R, int LEFT_FACT> int dispatch(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid)
+{
+#define GOOM_CASE(DPV, NWV) \
+    if (dp == DPV && nw == NWV) return launch_one<R, DPV, NWV, LEFT_FACT>(ctx, args, grid);
+    GOOM_CASE(16, 1)
+    GOOM_CASE(16, 2)
+    GOOM_CASE(32, 1)
+    GOOM_CASE(32, 2)
+    GOOM_CASE(32, 3)
+    GOOM_CASE(64, 1)
+    GOOM_CASE(64, 4)
+    GOOM_CASE(64, 5)
+    GOOM_CASE(128, 1)
+    GOOM_CASE(128, 8)
+#undef GOOM_CASE
+    return goom::fail(ctx, GOOM_EUNSUPPORTED, "no kernel for padded size %d with %d waves", dp, nw);
+}
+
+
+// one explicit instantiation per translation unit (they compile in parallel)
+int dispatch_f32_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid);
+int dispatch_f32_fact(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid);
+int dispatch_f64_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid);
+int dispatch_f64_fact(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid);
+
+} // namespace goom_chain

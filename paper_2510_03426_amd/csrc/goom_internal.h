@@ -1,0 +1,76 @@
+// Internal declarations shared by the libgoom sources (host side only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+
+#include "../../include/goom.h"
+
+struct goom_ctx {
+    int device;
+    hipStream_t stream;
+    std::string last_error;
+};
+
+namespace goom {
+
+int fail(goom_ctx *ctx, int status, const char *fmt, ...);
+int check_hip(goom_ctx *ctx, hipError_t e, const char *what);
+const char *thread_error();
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// ---- factored matrices kept in the workspace -------------------------------------
+// A running product is stored as real mantissas W[rows][cols_padded] (row-major, the
+// component type of the GOOM dtype) followed by one double per padded column holding a
+// power-of-two exponent: value[i][k] = W[i][k] * 2^e[k].
+struct FactLayout {
+    int rows_padded;   // DP: multiple of 16
+    int cols_padded;   // multiple of 16
+    size_t mant_bytes; // rows_padded * cols_padded * sizeof(component)
+    size_t stride;     // bytes between consecutive factored matrices (256-aligned)
+};
+FactLayout fact_layout(int dp, int m, int dtype);
+int padded_dim(int d);
+
+// ---- kernel launchers (defined in the .hip files) ---------------------------------
+struct ChainLaunch {
+    int dtype;            // GOOM_C64 / GOOM_C128
+    int n;                // rows of the left factors and of the outputs (= d for chains)
+    int d;                // columns of the left factors, rows of the state
+    int m;                // columns of the state
+    int left_fact;        // 0: left factors are GOOM matrices; 1: factored matrices (common exponent)
+    const void *left;     // first left factor of batch item 0
+    long long left_batch_stride; // bytes
+    long long left_step_stride;  // bytes
+    long long steps;      // left factors per batch item
+    long long chunk_len;  // steps per chain (chunk); chains per batch item = ceil(steps / chunk_len)
+    long long chunks_launched; // how many leading chunks per batch item get a workgroup
+    long long batch;
+    int init_mode;        // 0 identity, 1 factored, 2 GOOM, 3 zero
+    const void *init;     // per chain (factored) or per batch item (GOOM)
+    long long init_stride;       // bytes between consecutive chains (factored) / batch items (GOOM)
+    void *out_goom;       // NULL or GOOM outputs, [batch, steps, d, m]
+    int out_goom_last_only;      // 1: out_goom is [batch(, chunk), d, m], written at each chain's last step
+    void *out_fact_steps; // NULL or factored state before each step and after the last: (len + 1) per chain
+    void *out_fact_final; // NULL or factored final state per chain
+    int final_common_exponent;   // 1: out_fact_final columns share one exponent (usable as a left factor)
+    long long fact_stride;       // bytes between factored matrices in out_fact_*
+    int fact_cols;        // padded column count of factored states (init_mode 1, out_fact_*)
+    int left_fact_cols;   // padded column count of factored left factors
+    // linear recurrence with bias: one state column receives a bias vector every step
+    int bias_mode;        // 0 none, 1 GOOM vectors [batch, steps, d], 2 column d of the factored left factor
+    int bias_col;         // state column that receives the bias
+    const void *bias;
+};
+int launch_chain(goom_ctx *ctx, const ChainLaunch &a);
+
+int launch_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, uint32_t flags);
+int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype);
+
+} // namespace goom

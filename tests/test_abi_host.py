@@ -1,0 +1,100 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header
+declares, validates arguments before touching a device, and answers workspace queries.
+No compute call is made (no GPU here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2510_03426_amd import binding, build
+    build.build()
+    return binding.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "goom.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(goom_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2510_03426_amd import binding
+    names = declared_symbols()
+    assert len(names) >= 19
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+    assert lib.goom_version() == 100
+
+
+def err(lib):
+    return lib.goom_last_error(None).decode()
+
+
+def test_argument_validation_without_device(lib):
+    from paper_2510_03426_amd.binding import ScanOpts
+    p = C.c_void_p(0x1000)  # a plausible, aligned, never dereferenced pointer
+    EINVAL, EUNSUP, EWS = -1, -2, -3
+    # codecs
+    assert lib.goom_to_goom(None, p, p, 16, 7, 0) == EINVAL and "dtype" in err(lib)
+    assert lib.goom_to_goom(None, p, p, 16, 0, 4) == EINVAL and "flags" in err(lib)
+    assert lib.goom_to_goom(None, None, p, 16, 0, 0) == EINVAL and "null" in err(lib)
+    assert lib.goom_to_goom(None, C.c_void_p(0x1004), p, 16, 0, 0) == EINVAL and "aligned" in err(lib)
+    assert lib.goom_to_goom(None, p, p, 0, 0, 0) == 0  # empty input is a no-op
+    assert lib.goom_to_goom(None, p, p, 16, 0, 0) == EINVAL and "context" in err(lib)
+    assert lib.goom_from_goom(None, p, None, 16, 1) == EINVAL
+    # scan
+    o = ScanOpts(0, 0)
+    assert lib.goom_scan(None, p, None, p, 0, 8, 8, 1, 0, C.byref(o), None, 0) == EINVAL and "positive" in err(lib)
+    assert lib.goom_scan(None, p, None, p, 4, 129, 129, 1, 0, C.byref(o), None, 0) == EUNSUP
+    assert lib.goom_scan(None, p, None, p, 4, 8, 4, 1, 0, C.byref(o), None, 0) == EINVAL and "initial" in err(lib)
+    assert lib.goom_scan(None, p, None, p, 4, 8, 8, 1, 0, C.byref(ScanOpts(0, 9)), None, 0) == EINVAL
+    assert lib.goom_scan(None, p, None, p, 4, 8, 8, 1, 0, C.byref(ScanOpts(-1, 0)), None, 0) == EINVAL
+    assert lib.goom_scan(None, None, None, p, 4, 8, 8, 1, 0, None, None, 0) == EINVAL
+    need = lib.goom_scan_workspace_bytes(4096, 8, 8, 1, 0, C.byref(o))
+    assert need > 0
+    assert lib.goom_scan(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), None, 0) == EWS
+    assert lib.goom_scan(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), p, need - 1) == EWS and "small" in err(lib)
+    assert lib.goom_scan(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), C.c_void_p(0x1010), need) == EINVAL
+    assert lib.goom_scan(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), p, need) == EINVAL and "context" in err(lib)
+    assert lib.goom_reduce(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), None, 0) == EWS
+    # lmme
+    assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 0, 0, None, 0) == EUNSUP
+    assert lib.goom_lmme(None, p, p, p, 0, 8, 8, 8, 0, 0, None, 0) == EINVAL
+    assert lib.goom_lmme(None, p, p, p, 1, 8, 8, 8, 0, 2, None, 0) == EINVAL
+    # affine
+    assert lib.goom_affine_scan(None, p, None, None, p, 4, 8, 1, 0, None, None, 0) == EINVAL
+    assert lib.goom_affine_scan(None, p, p, None, p, 4, 128, 1, 0, None, None, 0) == EUNSUP
+    # context
+    assert lib.goom_create(None, 0, None) == EINVAL
+    ctx = C.c_void_p()
+    assert lib.goom_create(C.byref(ctx), -1, None) == EINVAL
+    assert lib.goom_status_name(-3).decode() == "GOOM_EWORKSPACE"
+
+
+def test_workspace_queries(lib):
+    from paper_2510_03426_amd.binding import ScanOpts
+    # one chunk needs no workspace; more chunks need room for chunk products and prefixes
+    assert lib.goom_scan_workspace_bytes(1, 64, 64, 1, 0, None) == 0
+    o = ScanOpts(1024, 0)
+    n = lib.goom_scan_workspace_bytes(1 << 20, 64, 64, 1, 0, C.byref(o))
+    per = 64 * 64 * 4 + 64 * 8
+    assert n == 2 * 1024 * ((per + 255) // 256 * 256)
+    assert lib.goom_reduce_workspace_bytes(1 << 20, 64, 64, 1, 0, C.byref(o)) == n // 2
+    assert lib.goom_scan_workspace_bytes(1 << 20, 64, 64, 1, 1, C.byref(o)) > n
+    assert lib.goom_scan_workspace_bytes(0, 64, 64, 1, 0, None) == 0
+    assert lib.goom_affine_scan_workspace_bytes(65536, 32, 128, 0, None) > 0
+    assert lib.goom_lmme_workspace_bytes(8192, 128, 128, 128, 0, 0) == 0
+
+
+def test_product_path_has_no_cpu_fallback():
+    # the package never imports the oracle, and the binding refuses to run without the library
+    import paper_2510_03426_amd.binding as b
+    src = open(b.__file__).read() + open(os.path.join(os.path.dirname(b.__file__), "__init__.py")).read()
+    assert "oracle" not in src

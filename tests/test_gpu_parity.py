@@ -1,0 +1,280 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Tolerances are the ones fixed for this build: codecs bit-exact;
+signs exact and log-magnitudes within 1e-3 absolute or 1e-4 relative (float components),
+1e-10 relative (double components), on every entry that is well conditioned at the
+component precision.  "Well conditioned" is decided by the oracle alone, two ways:
+  * the cancellation factor kappa of the sum that produced the entry is <= 2^10 (float
+    components) or 2^30 (double components);
+  * re-running the oracle on inputs whose log-magnitudes are perturbed by random amounts of
+    half a unit in the last place of the component type moves the entry by less than 1/16
+    of the tolerance and does not flip its sign (a finite-difference condition number: it
+    sees cancellation accumulated along the chain, which kappa of the last step does not).
+The fraction of entries excluded this way is bounded and printed."""
+import math
+import sys
+
+import numpy as np
+import pytest
+
+import synthetic_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    from paper_2510_03426_amd import Goom
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return Goom(0)
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    import torch
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def tolerance(ref_re, comp):
+    if comp == np.float32:
+        return np.maximum(1e-3, 1e-4 * np.abs(ref_re))
+    return np.maximum(1e-10, 1e-10 * np.abs(ref_re))
+
+
+def with_sensitivity(fn, arrays, comp, nprobe=2, seed=12345):
+    """Run oracle function fn(*arrays) -> (re, sg, kappa) and estimate, by finite differences,
+    how far half-ulp perturbations of the input log-magnitudes move each output.
+    Returns (re, sg, kappa, well_mask)."""
+    re, sg, kap = fn(*arrays)
+    eta = 2.0 ** -24 if comp == np.float32 else 2.0 ** -53
+    rng = np.random.default_rng(seed)
+    sens = np.zeros_like(re)
+    for _ in range(nprobe):
+        pert = []
+        for a in arrays:
+            if a is None:
+                pert.append(None)
+                continue
+            z = a.astype(np.complex128)
+            z.real += eta * rng.standard_normal(a.shape) * np.where(np.isfinite(a.real), 1.0, 0.0)
+            pert.append(z)
+        pre, psg, _ = fn(*pert)
+        with np.errstate(invalid="ignore"):
+            dlt = np.abs(pre - re)
+        dlt[np.isnan(dlt)] = 0.0  # both -inf
+        dlt[psg != sg] = np.inf
+        sens = np.maximum(sens, dlt)
+    limit = 2.0 ** 10 if comp == np.float32 else 2.0 ** 30
+    well = (kap <= limit) & (sens <= tolerance(re, comp) / 16)
+    return re, sg, kap, well
+
+
+def compare(got, ref_re, ref_sg, kappa=None, name="", max_ill_fraction=0.005, well=None):
+    """got: complex numpy array from the GPU; ref: oracle working form."""
+    comp = np.float32 if got.dtype == np.complex64 else np.float64
+    pi = comp(np.pi)
+    im = got.imag
+    assert np.all((im == 0) | (im == pi)), f"{name}: imaginary parts other than 0 / pi"
+    got_sg = (im != 0)
+    got_re = got.real.astype(np.float64)
+    if kappa is None:
+        kappa = np.ones_like(ref_re)
+    limit = 2.0 ** 10 if comp == np.float32 else 2.0 ** 30
+    well = (kappa <= limit) if well is None else (well & (kappa <= limit))
+    ill_frac = 1.0 - well.mean()
+    both_zero = np.isneginf(ref_re) & np.isneginf(got_re)
+    one_zero = np.isneginf(ref_re) ^ np.isneginf(got_re)
+    assert not np.any(one_zero & well), f"{name}: zero / non-zero mismatch on {np.sum(one_zero & well)} entries"
+    finite = well & ~both_zero & ~one_zero
+    sign_bad = finite & (got_sg != ref_sg.astype(bool))
+    assert not np.any(sign_bad), f"{name}: {sign_bad.sum()} sign mismatches of {finite.sum()} (first at {np.argwhere(sign_bad)[0]})"
+    with np.errstate(invalid="ignore"):
+        diff = np.abs(got_re - ref_re)
+    tol = tolerance(ref_re, comp)
+    bad = finite & (diff > tol)
+    worst = np.nanmax(np.where(finite, diff / tol, 0.0)) if finite.any() else 0.0
+    say(f"  [{name}] entries={got.size} ill-conditioned={ill_frac:.2e} worst |dre|/tol={worst:.3g}")
+    assert not np.any(bad), f"{name}: {bad.sum()} log-magnitudes out of tolerance (worst ratio {worst:.3g})"
+    assert ill_frac <= max_ill_fraction, f"{name}: {ill_frac:.3%} ill-conditioned entries"
+
+
+# ------------------------------------------------------------------------------ codecs
+
+@pytest.mark.parametrize("comp", [np.float32, np.float64])
+def test_codecs_bit_exact(G, oracle, comp):
+    rng = np.random.default_rng(101)
+    n = (1 << 20) + 3  # ragged tail
+    x = np.concatenate([
+        si.normal_f32(si.BASE_SEED, 50, n // 2).astype(comp),
+        (np.exp(rng.uniform(-85, 85, n - n // 2 - 8)) * rng.choice([-1.0, 1.0], n - n // 2 - 8)).astype(comp),
+        np.array([0.0, -0.0, 1.0, -1.0, np.inf, -np.inf, np.finfo(comp).tiny, -np.finfo(comp).max], dtype=comp),
+    ])
+    say(f"codec {comp.__name__}: n={x.size}")
+    for flags in (0, 1):
+        want = oracle.to_goom(x, zero_floor=bool(flags))
+        got = host(G.to_goom(dev(x), flags=flags))
+        if comp == np.float32:
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), \
+                f"{np.sum(got.view(np.uint32) != want.view(np.uint32))} words differ"
+        else:
+            # double components: both sides round a correctly rounded double log once; equal bits expected
+            # except where two different double-precision logs disagree in the last place
+            neq = got.view(np.uint64) != want.view(np.uint64)
+            ulp = np.abs(got.real - want.real) / np.maximum(np.spacing(np.abs(want.real)), 5e-324)
+            say(f"  double codec: {neq.sum()} of {neq.size} words differ, max {np.nanmax(np.where(np.isfinite(ulp), ulp, 0)):.1f} ulp")
+            assert np.array_equal(got.imag, want.imag)
+            assert np.all((ulp <= 1.0) | ~np.isfinite(want.real))
+    z = oracle.to_goom(x)
+    z = z[np.isfinite(z.real) | np.isneginf(z.real)]
+    want = oracle.from_goom(z)
+    got = host(G.from_goom(dev(z)))
+    if comp == np.float32:
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), \
+            f"{np.sum(got.view(np.uint32) != want.view(np.uint32))} decoded words differ"
+    else:
+        ulp = np.abs(got - want) / np.spacing(np.abs(want))
+        assert np.all(ulp <= 1.0)
+    # empty input
+    import torch
+    assert G.to_goom(torch.empty(0, dtype=torch.float32, device="cuda")).numel() == 0
+
+
+def test_decode_accepts_any_phase_multiple(G, oracle):
+    z = np.array([3 + 2j * math.pi, 3 + 4j * math.pi, 3 + 1j * math.pi, 3 - 3j * math.pi, -np.inf + 0j, 200 + 0j],
+                 dtype=np.complex64)
+    got = host(G.from_goom(dev(z)))
+    want = oracle.from_goom(z)
+    assert np.array_equal(got, want)
+    assert abs(got[0] - 20.0855) < 1e-3 and got[0] == got[1] and got[2] < 0 and got[3] < 0 and got[4] == 0 and np.isinf(got[5])
+
+
+# -------------------------------------------------------------------------------- LMME
+
+@pytest.mark.parametrize("shape", [(1, 8, 8, 8), (3, 16, 16, 16), (2, 5, 7, 3), (2, 64, 64, 64), (2, 128, 128, 128),
+                                   (1, 33, 20, 1), (2, 1, 1, 1), (1, 100, 128, 60)])
+def test_lmme_matches_oracle(G, oracle, shape):
+    b, n, d, m = shape
+    say(f"lmme batch={b} n={n} d={d} m={m}")
+    A = oracle.to_goom(si.normal_f32(si.BASE_SEED + 20, 7, b * n * d).reshape(b, n, d))
+    B = oracle.to_goom(si.normal_f32(si.BASE_SEED + 21, 8, b * d * m).reshape(b, d, m))
+    A[0, 0, 0] = -np.inf  # a zero entry
+    re, sg, kap = oracle.lmme(A, B, return_kappa=True)
+    got = host(G.lmme(dev(A), dev(B)))
+    compare(got, re, sg, kap, name=f"lmme{shape}", max_ill_fraction=0.02)
+
+
+def test_lmme_far_outside_float_range(G, oracle):
+    # log-magnitudes of order +-1e5: no float could hold the values, row/column shifts absorb them
+    rng = np.random.default_rng(5)
+    b, n, d, m = 2, 32, 32, 32
+    A = oracle.to_goom(si.normal_f32(si.BASE_SEED + 22, 7, b * n * d).reshape(b, n, d))
+    B = oracle.to_goom(si.normal_f32(si.BASE_SEED + 23, 8, b * d * m).reshape(b, d, m))
+    A.real += rng.uniform(-1e5, 1e5, (b, n, 1)).astype(np.float32)
+    B.real += rng.uniform(-1e5, 1e5, (b, 1, m)).astype(np.float32)
+    B[0, :, 3] = -np.inf  # an all-zero column
+    A[1, 5, :] = -np.inf  # an all-zero row
+    re, sg, kap = oracle.lmme(A, B, return_kappa=True)
+    got = host(G.lmme(dev(A), dev(B)))
+    assert np.all(np.isneginf(got.real[0, :, 3])) and np.all(np.isneginf(got.real[1, 5, :]))
+    compare(got, re, sg, kap, name="lmme wide", max_ill_fraction=0.02)
+
+
+def test_lmme_double_components(G, oracle):
+    b, n, d, m = 2, 48, 64, 40
+    A = oracle.to_goom(si.normal_f32(si.BASE_SEED + 24, 7, b * n * d).reshape(b, n, d).astype(np.float64))
+    B = oracle.to_goom(si.normal_f32(si.BASE_SEED + 25, 8, b * d * m).reshape(b, d, m).astype(np.float64))
+    re, sg, kap = oracle.lmme(A, B, return_kappa=True)
+    got = host(G.lmme(dev(A), dev(B)))
+    compare(got, re, sg, kap, name="lmme c128")
+
+
+# -------------------------------------------------------------------------------- scan
+
+def run_scan_case(G, oracle, T, d, chunk_len, m=None, batch=1, seed=0, dtype=np.float32, name=""):
+    x = si.normal_f32(si.BASE_SEED + 30 + seed, 1, batch * T * d * d).reshape(batch, T, d, d).astype(dtype)
+    Z = oracle.to_goom(x)
+    init = None
+    if m is not None:
+        init = oracle.to_goom(si.normal_f32(si.BASE_SEED + 31 + seed, 2, batch * d * m).reshape(batch, d, m).astype(dtype))
+    say(f"scan {name}: T={T} d={d} m={m} batch={batch} chunk_len={chunk_len} {np.dtype(dtype).name}")
+    out = host(G.scan(dev(Z), None if init is None else dev(init), chunk_len=chunk_len))
+    red = host(G.reduce(dev(Z), None if init is None else dev(init), chunk_len=chunk_len))
+    comp = np.dtype(dtype).type
+    for b in range(batch):
+        fn = lambda mats, ini: oracle.scan(mats, init=ini, return_kappa=True)
+        re, sg, kap, well = with_sensitivity(fn, [Z[b], None if init is None else init[b]], comp)
+        compare(out[b], re, sg, kap, name=f"{name} scan b{b}", max_ill_fraction=0.03, well=well)
+        compare(red[b], re[-1], sg[-1], kap[-1], name=f"{name} reduce b{b}", max_ill_fraction=0.06, well=well[-1])
+    return out
+
+
+def test_scan_tiny_config(G, oracle):
+    # T = 256 chain of 8 x 8 matrices: all 256 prefix products
+    run_scan_case(G, oracle, 256, 8, 0, name="cfg1 default chunks")
+    run_scan_case(G, oracle, 256, 8, 256, name="cfg1 one chunk")
+    run_scan_case(G, oracle, 256, 8, 1, name="cfg1 chunk_len 1")
+
+
+@pytest.mark.parametrize("T,d,chunk", [(37, 16, 5), (300, 32, 64), (700, 64, 100), (130, 128, 32), (64, 5, 7), (50, 33, 16),
+                                       (1, 64, 0), (2, 64, 1)])
+def test_scan_sizes_and_ragged_tails(G, oracle, T, d, chunk):
+    run_scan_case(G, oracle, T, d, chunk, name=f"T{T}d{d}")
+
+
+def test_scan_with_initial_state_and_batch(G, oracle):
+    run_scan_case(G, oracle, 120, 32, 16, m=32, batch=3, seed=1, name="init square batch3")
+    run_scan_case(G, oracle, 120, 64, 25, m=1, batch=2, seed=2, name="init vector")
+    run_scan_case(G, oracle, 90, 16, 8, m=24, batch=1, seed=3, name="init wide")
+
+
+def test_scan_double_components(G, oracle):
+    run_scan_case(G, oracle, 200, 16, 16, seed=4, dtype=np.float64, name="c128 d16")
+    run_scan_case(G, oracle, 96, 64, 24, seed=5, dtype=np.float64, name="c128 d64")
+
+
+def test_scan_is_deterministic(G, oracle):
+    Z = oracle.to_goom(si.normal_chain(si.BASE_SEED + 40, 512, 64))
+    a = host(G.scan(dev(Z), chunk_len=64))
+    b = host(G.scan(dev(Z), chunk_len=64))
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+def test_scan_beyond_float_range(G, oracle):
+    # 4096 steps of 64 x 64: log-magnitudes reach ~8500, far past float and double range
+    T, d = 4096, 64
+    Z = oracle.to_goom(si.normal_chain(si.BASE_SEED + 41, T, d))
+    out = host(G.scan(dev(Z)))
+    sample = list(range(0, T, 97)) + [T - 1]
+    fn = lambda mats: oracle.ScanStream(d, scaled=True).advance(mats, sample_t=sample, return_kappa=True)
+    re, sg, kap, well = with_sensitivity(fn, [Z], np.float32, nprobe=1)
+    compare(out[sample], re, sg, kap, name="T4096 d64", max_ill_fraction=0.03, well=well)
+    assert out.real[-1].max() > 8000
+    lam = 0.5 * (math.log(2) + 3.4499)  # (ln 2 + psi(32)) / 2
+    assert abs(out.real[-1].max() / T - lam) < 0.05
+
+
+# ------------------------------------------------------------------------------ affine
+
+@pytest.mark.parametrize("T,d,batch,chunk", [(64, 8, 2, 0), (300, 32, 3, 32), (100, 16, 1, 9), (1, 32, 2, 0), (257, 64, 1, 40)])
+def test_affine_scan_matches_oracle(G, oracle, T, d, batch, chunk):
+    A, b = si.recurrence_inputs(si.BASE_SEED + 50, batch, T, d)
+    Az, bz = oracle.to_goom(A), oracle.to_goom(b)
+    say(f"affine T={T} d={d} batch={batch} chunk={chunk}")
+    fn = lambda a_, b_, h_: oracle.affine_scan(a_, b_, h0=h_, return_kappa=True)
+    re, sg, kap, well = with_sensitivity(fn, [Az, bz, None], np.float32)
+    got = host(G.affine_scan(dev(Az), dev(bz), chunk_len=chunk))
+    compare(got, re, sg, kap, name=f"affine T{T}d{d}", max_ill_fraction=0.03, well=well)
+    h0 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 51, 9, batch * d).reshape(batch, d))
+    re, sg, kap, well = with_sensitivity(fn, [Az, bz, h0], np.float32)
+    got = host(G.affine_scan(dev(Az), dev(bz), dev(h0), chunk_len=chunk))
+    compare(got, re, sg, kap, name=f"affine h0 T{T}d{d}", max_ill_fraction=0.03, well=well)
