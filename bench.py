@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark of the GOOM prefix scan on one MI355X.
+
+One "step" is one whole inclusive prefix scan (all three phases: chunk products, carry
+chain, fix-up with every output stored) of the long-chain workload: T = 1,048,576 real
+64 x 64 matrices with i.i.d. N(0, 1) entries, given as complex64 GOOMs already resident
+in HBM; 34 GB in, 34 GB out.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--T N] [--d N] [--chunk-len N]
+
+Everything runs on one GPU; --gpus above 1 is refused.
+"""
+import argparse
+import json
+import sys
+import time
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix rate, published
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--T", type=int, default=1 << 20)
+    ap.add_argument("--d", type=int, default=64)
+    ap.add_argument("--chunk-len", type=int, default=0)
+    ap.add_argument("--cpu-sample-steps", type=int, default=2048,
+                    help="leading steps of the chain the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs")
+    ap.add_argument("--no-extras", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2510_03426_amd import Goom
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    T, d = args.T, args.d
+    dev = torch.device("cuda", 0)
+    g = Goom(0)
+
+    # ---- synthetic input: N(0,1) reals drawn on the device, encoded by the library's codec
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(251003426 * 10 + 2)
+    z = torch.empty((T, d, d), dtype=torch.complex64, device=dev)
+    blk = max(1, (1 << 28) // (d * d))
+    t_codec = 0.0
+    for t0 in range(0, T, blk):
+        t1 = min(T, t0 + blk)
+        x = torch.randn((t1 - t0, d, d), dtype=torch.float32, device=dev, generator=gen)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        g.to_goom(x, out=z[t0:t1])
+        torch.cuda.synchronize()
+        t_codec += time.perf_counter() - c0
+        del x
+    out = torch.empty((T, d, d), dtype=torch.complex64, device=dev)
+    print(f"# input ready: {z.numel() * 8 / 1e9:.2f} GB of GOOMs; to_goom ran at "
+          f"{z.numel() * 12 / t_codec / 1e9:.0f} GB/s", file=sys.stderr, flush=True)
+
+    def step():
+        g.scan(z, chunk_len=args.chunk_len, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    products_per_s = T / (ms_per_step * 1e-3)
+
+    # ---- per-kernel durations from HIP events on the library's stream
+    g.profile_enable(True)
+    kern = {}
+    nprof = max(1, min(args.steps, 5))
+    for _ in range(nprof):
+        step()
+        for label, ms in g.profile_records():
+            kern.setdefault(label, []).append(ms)
+    g.profile_enable(False)
+    kern_avg = {k: sum(v) / len(v) for k, v in kern.items()}
+    dominant = max(kern_avg, key=kern_avg.get)
+    # algorithmic bytes of the fix-up kernel: every matrix read once (complex64) and every
+    # prefix written once (complex64): 2 * 8 * d * d bytes per product
+    if dominant.endswith("fixup_outputs") or dominant == "scan_single_chunk":
+        alg_bytes = T * 2 * 8 * d * d
+    else:
+        alg_bytes = T * 8 * d * d
+    achieved_gbs = alg_bytes / (kern_avg[dominant] * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": dominant, "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
+        "traffic": args.traffic_bytes, "algorithmic_bytes_per_launch": alg_bytes,
+        "avg_launch_ms": round(kern_avg[dominant], 4),
+    }
+    # matrix-core work actually executed: one d^3 product per matrix in phase 1, one per chunk in
+    # phase 2, one per matrix in phase 3
+    flops_exec = 2.0 * d ** 3 * (2 * T)
+    lmme_tflops = flops_exec / (ms_per_step * 1e-3) / 1e12
+    phase_tflops = {k: round(2.0 * d ** 3 * T / (v * 1e-3) / 1e12, 2) for k, v in kern_avg.items()
+                    if "phase1" in k or "phase3" in k}
+
+    result = {
+        "metric": "GOOM matrix products scanned per second (inclusive prefix scan, all prefixes stored)",
+        "value": round(products_per_s, 1), "unit": "products/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"prefix scan of T={T} real {d}x{d} N(0,1) matrices as complex64 GOOMs, "
+                               f"in HBM, {T * d * d * 8 / 1e9:.1f} GB in and out",
+                   "T": T, "d": d, "chunk_len": args.chunk_len},
+        "lmme": {"tflops_executed": round(lmme_tflops, 2),
+                 "pct_of_fp32_mfma_peak": round(100 * lmme_tflops / MFMA_F32_PEAK_TFLOPS, 2),
+                 "per_phase_tflops": phase_tflops},
+        "kernels_ms": {k: round(v, 4) for k, v in kern_avg.items()},
+        "roofline": roofline,
+    }
+
+    # ---- extras: the reduction variant (final product only), same input
+    if not args.no_extras:
+        fin = torch.empty((d, d), dtype=torch.complex64, device=dev)
+        g.reduce(z, chunk_len=args.chunk_len, out=fin)
+        torch.cuda.synchronize()
+        r0 = time.perf_counter()
+        for _ in range(3):
+            g.reduce(z, chunk_len=args.chunk_len, out=fin)
+        torch.cuda.synchronize()
+        rms = (time.perf_counter() - r0) / 3 * 1e3
+        result["reduce"] = {"ms": round(rms, 4), "products_per_s": round(T / (rms * 1e-3), 1),
+                            "hbm_gbs": round(T * 8 * d * d / (rms * 1e-3) / 1e9, 1)}
+        result["to_goom_gbs"] = round(z.numel() * 12 / t_codec / 1e9, 1)
+
+    # ---- CPU oracle on a bounded sample of the same workload (reported, not a target)
+    if args.cpu_sample_steps > 0:
+        from oracle import goom_oracle as oracle
+        S = min(T, args.cpu_sample_steps)
+        zs = z[:S].cpu().numpy()
+        c0 = time.perf_counter()
+        re, sg = oracle.scan(zs)
+        cpu_s = time.perf_counter() - c0
+        result["cpu_baseline"] = {
+            "value": round(S / cpu_s, 2), "unit": "products/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {S} steps of the same chain (definitional log-sum-exp scan in double), {cpu_s:.1f} s",
+        }
+        # the GPU result on the sampled prefix must agree with the oracle
+        got = out[:S].cpu().numpy()
+        well = np.isfinite(re)
+        err = np.abs(got.real.astype(np.float64) - re)[well]
+        tol = np.maximum(1e-3, 1e-4 * np.abs(re[well]))
+        result["cpu_baseline"]["gpu_entries_within_tolerance"] = round(float(np.mean(err <= tol)), 6)
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

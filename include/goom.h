@@ -91,6 +91,16 @@ int goom_set_stream(goom_ctx *ctx, void *stream);
 const char *goom_last_error(const goom_ctx *ctx);
 const char *goom_status_name(int status);
 
+/* ---- per-kernel timing (measurement aid, not part of the method) ------------------- */
+
+/* When enabled, every kernel a compute call enqueues is bracketed by HIP events on the
+ * context's stream.  Records are cleared at the start of each compute call.
+ * goom_profile_get waits for record i of the last call and returns the kernel's label
+ * (a static string naming the phase) and its elapsed time in milliseconds. */
+int goom_profile_enable(goom_ctx *ctx, int enable);
+int goom_profile_count(const goom_ctx *ctx);
+int goom_profile_get(goom_ctx *ctx, int i, const char **label, float *milliseconds);
+
 /* ---- codecs (paper Section 3.1) -------------------------------------------------- */
 
 /* Real floats -> GOOMs: y[i] = (log|x[i]|, x[i] < 0 ? pi : 0).  x: n floats (GOOM_C64)

@@ -21,7 +21,7 @@ RESET_ALWAYS, RESET_COLINEAR, RESET_NEVER = 1, 0, -1
 
 EXPORTS = [
     "goom_version", "goom_create", "goom_destroy", "goom_set_stream", "goom_last_error",
-    "goom_status_name", "goom_to_goom", "goom_from_goom", "goom_lmme", "goom_lmme_workspace_bytes",
+    "goom_status_name", "goom_profile_enable", "goom_profile_count", "goom_profile_get", "goom_to_goom", "goom_from_goom", "goom_lmme", "goom_lmme_workspace_bytes",
     "goom_scan", "goom_scan_workspace_bytes", "goom_reduce", "goom_reduce_workspace_bytes",
     "goom_scan_reset", "goom_scan_reset_workspace_bytes", "goom_lyapunov_spectrum",
     "goom_affine_scan", "goom_affine_scan_workspace_bytes",
@@ -64,6 +64,9 @@ def load_library():
     lib.goom_last_error.restype = C.c_char_p
     lib.goom_status_name.argtypes = [i32]
     lib.goom_status_name.restype = C.c_char_p
+    lib.goom_profile_enable.argtypes = [vp, i32]
+    lib.goom_profile_count.argtypes = [vp]
+    lib.goom_profile_get.argtypes = [vp, i32, C.POINTER(C.c_char_p), C.POINTER(C.c_float)]
     lib.goom_to_goom.argtypes = [vp, vp, vp, sz, i32, u32]
     lib.goom_from_goom.argtypes = [vp, vp, vp, sz, i32]
     lib.goom_lmme.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i32, u32, vp, sz]
@@ -152,6 +155,18 @@ class Goom:
     def set_stream(self, stream):
         self._stream = stream
         self._check(self.lib.goom_set_stream(self._ctx, C.c_void_p(stream.cuda_stream)))
+
+    def profile_enable(self, on: bool = True):
+        self._check(self.lib.goom_profile_enable(self._ctx, int(on)))
+
+    def profile_records(self):
+        """[(label, milliseconds)] for the kernels of the last compute call (waits for them)."""
+        out = []
+        for i in range(self.lib.goom_profile_count(self._ctx)):
+            label, ms = C.c_char_p(), C.c_float()
+            self._check(self.lib.goom_profile_get(self._ctx, i, C.byref(label), C.byref(ms)))
+            out.append((label.value.decode(), float(ms.value)))
+        return out
 
     def workspace(self, nbytes: int):
         """A cached 256-byte aligned scratch tensor of at least nbytes (None for 0)."""

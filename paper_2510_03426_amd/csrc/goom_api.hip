@@ -30,6 +30,35 @@ int check_hip(goom_ctx *ctx, hipError_t e, const char *what)
     return fail(ctx, GOOM_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+void prof_reset(goom_ctx *ctx)
+{
+    if (!ctx) return;
+    for (auto &r : ctx->prof) ctx->prof_pool.push_back(r);
+    ctx->prof.clear();
+}
+
+void prof_begin(goom_ctx *ctx, const char *label)
+{
+    if (!ctx || !ctx->profile) return;
+    goom_prof_rec r;
+    if (!ctx->prof_pool.empty()) {
+        r = ctx->prof_pool.back();
+        ctx->prof_pool.pop_back();
+    } else {
+        if (hipEventCreate(&r.start) != hipSuccess) return;
+        if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return; }
+    }
+    r.label = label ? label : "kernel";
+    (void)hipEventRecord(r.start, ctx->stream);
+    ctx->prof.push_back(r);
+}
+
+void prof_end(goom_ctx *ctx)
+{
+    if (!ctx || !ctx->profile || ctx->prof.empty()) return;
+    (void)hipEventRecord(ctx->prof.back().stop, ctx->stream);
+}
+
 static size_t comp_bytes(int dtype) { return dtype == GOOM_C64 ? 4 : 8; }
 
 static int check_common(goom_ctx *ctx, int dtype)
@@ -43,6 +72,7 @@ static int check_common(goom_ctx *ctx, int dtype)
 static int need_ctx(goom_ctx *ctx)
 {
     if (!ctx) return fail(nullptr, GOOM_EINVAL, "null context");
+    prof_reset(ctx);
     return check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice");
 }
 
@@ -139,6 +169,7 @@ static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, lon
         l.init_stride = (long long)d * m * cb;
         l.out_goom = P;
         l.out_goom_last_only = final_only ? 1 : 0;
+        l.label = "scan_single_chunk";
         return launch_chain(ctx, l);
     }
 
@@ -159,6 +190,7 @@ static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, lon
         l.final_common_exponent = 1;
         l.fact_stride = (long long)p.tot.stride;
         l.fact_cols = p.tot.cols_padded;
+        l.label = "scan_phase1_chunk_products";
         if (int s = launch_chain(ctx, l)) return s;
     }
     { // phase 2: prefixes of the chunk products (one chain per batch item)
@@ -183,6 +215,7 @@ static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, lon
             l.fact_stride = (long long)p.car.stride;
             l.fact_cols = p.car.cols_padded;
         }
+        l.label = "scan_phase2_carry_chain";
         if (int s = launch_chain(ctx, l)) return s;
         if (final_only) return GOOM_OK;
     }
@@ -201,6 +234,7 @@ static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, lon
         l.fact_stride = (long long)p.car.stride;
         l.fact_cols = p.car.cols_padded;
         l.out_goom = P;
+        l.label = "scan_phase3_fixup_outputs";
         return launch_chain(ctx, l);
     }
 }
@@ -251,7 +285,35 @@ int goom_create(goom_ctx **out, int device, void *stream)
 
 int goom_destroy(goom_ctx *ctx)
 {
+    if (!ctx) return GOOM_OK;
+    prof_reset(ctx);
+    for (auto &r : ctx->prof_pool) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
     delete ctx;
+    return GOOM_OK;
+}
+
+int goom_profile_enable(goom_ctx *ctx, int enable)
+{
+    if (!ctx) return fail(nullptr, GOOM_EINVAL, "null context");
+    ctx->profile = enable != 0;
+    return GOOM_OK;
+}
+
+int goom_profile_count(const goom_ctx *ctx) { return ctx ? (int)ctx->prof.size() : 0; }
+
+int goom_profile_get(goom_ctx *ctx, int i, const char **label, float *milliseconds)
+{
+    if (!ctx) return fail(nullptr, GOOM_EINVAL, "null context");
+    if (i < 0 || i >= (int)ctx->prof.size()) return fail(ctx, GOOM_EINVAL, "no profiling record %d", i);
+    goom_prof_rec &r = ctx->prof[i];
+    if (int s = check_hip(ctx, hipEventSynchronize(r.stop), "hipEventSynchronize")) return s;
+    float ms = 0.f;
+    if (int s = check_hip(ctx, hipEventElapsedTime(&ms, r.start, r.stop), "hipEventElapsedTime")) return s;
+    if (label) *label = r.label;
+    if (milliseconds) *milliseconds = ms;
     return GOOM_OK;
 }
 
@@ -319,6 +381,7 @@ int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batc
     l.init = B;
     l.init_stride = (long long)d * m * cb;
     l.out_goom = C;
+    l.label = "lmme";
     return launch_chain(ctx, l);
 }
 
@@ -393,6 +456,7 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
         l.init = h0;
         l.init_stride = (long long)d * cb;
         l.out_goom = H;
+        l.label = "affine_single_chunk";
         return launch_chain(ctx, l);
     }
     unsigned char *totals = static_cast<unsigned char *>(ws);
@@ -408,6 +472,7 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
         l.final_common_exponent = 1;
         l.fact_stride = (long long)p.tot.stride;
         l.fact_cols = p.tot.cols_padded;
+        l.label = "affine_phase1_chunk_products";
         if (int s = launch_chain(ctx, l)) return s;
     }
     { // phase 2: h at the chunk boundaries
@@ -434,6 +499,7 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
         l.out_fact_steps = carries;
         l.fact_stride = (long long)p.car.stride;
         l.fact_cols = p.car.cols_padded;
+        l.label = "affine_phase2_carry_chain";
         if (int s = launch_chain(ctx, l)) return s;
     }
     { // phase 3: matrix-vector walk of every chunk
@@ -448,6 +514,7 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
         l.fact_stride = (long long)p.car.stride;
         l.fact_cols = p.car.cols_padded;
         l.out_goom = H;
+        l.label = "affine_phase3_outputs";
         return launch_chain(ctx, l);
     }
 }

@@ -63,8 +63,8 @@ int launch_chain(goom_ctx *ctx, const ChainLaunch &l)
     a.bias = static_cast<const unsigned char *>(l.bias);
     const long long grid = l.batch * l.chunks_launched;
     if (l.dtype == GOOM_C64)
-        return l.left_fact ? goom_chain::dispatch_f32_fact(ctx, a, dp, nw, grid) : goom_chain::dispatch_f32_goom(ctx, a, dp, nw, grid);
-    return l.left_fact ? goom_chain::dispatch_f64_fact(ctx, a, dp, nw, grid) : goom_chain::dispatch_f64_goom(ctx, a, dp, nw, grid);
+        return l.left_fact ? goom_chain::dispatch_f32_fact(ctx, a, dp, nw, grid, l.label) : goom_chain::dispatch_f32_goom(ctx, a, dp, nw, grid, l.label);
+    return l.left_fact ? goom_chain::dispatch_f64_fact(ctx, a, dp, nw, grid, l.label) : goom_chain::dispatch_f64_goom(ctx, a, dp, nw, grid, l.label);
 }
 
 } // namespace goom

@@ -494,7 +494,7 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
     if (a.out_fact_final) store_fact(a.out_fact_final + chain_global * a.fact_stride, a.final_common_exponent != 0);
 }
 
-template <typename R, int DP, int NW, int LEFT_FACT> int launch_one(goom_ctx *ctx, const ChainArgs &args, long long grid)
+template <typename R, int DP, int NW, int LEFT_FACT> int launch_one(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
 {
     constexpr int LDA = DP + Comp<R>::kPad;
     const size_t buf = (size_t)DP * LDA * sizeof(R) + (size_t)DP * sizeof(double);
@@ -507,14 +507,16 @@ template <typename R, int DP, int NW, int LEFT_FACT> int launch_one(goom_ctx *ct
     }
     if (grid <= 0) return GOOM_OK;
     if (grid > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many chains for one launch (%lld)", grid);
+    goom::prof_begin(ctx, label);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds, ctx->stream, args);
+    goom::prof_end(ctx);
     return goom::check_hip(ctx, hipGetLastError(), "launch chain_kernel");
 }
 
-template <typename R, int LEFT_FACT> int dispatch(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid)
+template <typename R, int LEFT_FACT> int dispatch(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label)
 {
 #define GOOM_CASE(DPV, NWV) \
-    if (dp == DPV && nw == NWV) return launch_one<R, DPV, NWV, LEFT_FACT>(ctx, args, grid);
+    if (dp == DPV && nw == NWV) return launch_one<R, DPV, NWV, LEFT_FACT>(ctx, args, grid, label);
     GOOM_CASE(16, 1)
     GOOM_CASE(16, 2)
     GOOM_CASE(32, 1)
@@ -531,9 +533,9 @@ template <typename R, int LEFT_FACT> int dispatch(goom_ctx *ctx, const ChainArgs
 
 
 // one explicit instantiation per translation unit (they compile in parallel)
-int dispatch_f32_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid);
-int dispatch_f32_fact(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid);
-int dispatch_f64_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid);
-int dispatch_f64_fact(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid);
+int dispatch_f32_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label);
+int dispatch_f32_fact(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label);
+int dispatch_f64_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label);
+int dispatch_f64_fact(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label);
 
 } // namespace goom_chain

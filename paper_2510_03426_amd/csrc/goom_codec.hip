@@ -103,6 +103,7 @@ int launch_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, u
 {
     if (n == 0) return GOOM_OK;
     const int zf = (flags & GOOM_ZERO_FLOOR) ? 1 : 0;
+    prof_begin(ctx, "to_goom");
     if (dtype == GOOM_C64) {
         hipLaunchKernelGGL(to_goom_f32_kernel, dim3(grid_for(n / 4 + 4)), dim3(256), 0, ctx->stream,
                            static_cast<const float *>(x), static_cast<float *>(y), n, zf);
@@ -110,12 +111,14 @@ int launch_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, u
         hipLaunchKernelGGL(to_goom_f64_kernel, dim3(grid_for(n)), dim3(256), 0, ctx->stream,
                            static_cast<const double *>(x), static_cast<double *>(y), n, zf);
     }
+    prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch to_goom");
 }
 
 int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype)
 {
     if (n == 0) return GOOM_OK;
+    prof_begin(ctx, "from_goom");
     if (dtype == GOOM_C64) {
         hipLaunchKernelGGL(from_goom_f32_kernel, dim3(grid_for(n)), dim3(256), 0, ctx->stream,
                            static_cast<const float *>(y), static_cast<float *>(x), n);
@@ -123,6 +126,7 @@ int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype)
         hipLaunchKernelGGL(from_goom_f64_kernel, dim3(grid_for(n)), dim3(256), 0, ctx->stream,
                            static_cast<const double *>(y), static_cast<double *>(x), n);
     }
+    prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch from_goom");
 }
 

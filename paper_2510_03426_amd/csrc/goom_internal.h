@@ -7,13 +7,22 @@
 #include <cstdint>
 #include <cstdio>
 #include <string>
+#include <vector>
 
 #include "../../include/goom.h"
+
+struct goom_prof_rec {
+    const char *label;
+    hipEvent_t start, stop;
+};
 
 struct goom_ctx {
     int device;
     hipStream_t stream;
     std::string last_error;
+    bool profile = false;
+    std::vector<goom_prof_rec> prof;     // records of the last compute call
+    std::vector<goom_prof_rec> prof_pool; // events kept for reuse
 };
 
 namespace goom {
@@ -21,6 +30,11 @@ namespace goom {
 int fail(goom_ctx *ctx, int status, const char *fmt, ...);
 int check_hip(goom_ctx *ctx, hipError_t e, const char *what);
 const char *thread_error();
+
+// event bracketing of kernel launches (no-ops unless profiling is enabled)
+void prof_reset(goom_ctx *ctx);
+void prof_begin(goom_ctx *ctx, const char *label);
+void prof_end(goom_ctx *ctx);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -67,6 +81,7 @@ struct ChainLaunch {
     int bias_mode;        // 0 none, 1 GOOM vectors [batch, steps, d], 2 column d of the factored left factor
     int bias_col;         // state column that receives the bias
     const void *bias;
+    const char *label;    // phase name for profiling records
 };
 int launch_chain(goom_ctx *ctx, const ChainLaunch &a);
 

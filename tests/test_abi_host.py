@@ -26,7 +26,7 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported(lib):
     from paper_2510_03426_amd import binding
     names = declared_symbols()
-    assert len(names) >= 19
+    assert len(names) >= 22
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(binding.EXPORTS) == names
