@@ -50,6 +50,8 @@ int launch_chain(goom_ctx *ctx, const ChainLaunch &l)
     a.init_mode = l.init_mode;
     a.init = static_cast<const unsigned char *>(l.init);
     a.init_stride = l.init_stride;
+    a.init_group = l.init_group;
+    a.init_ngroups = l.init_ngroups;
     a.out_goom = static_cast<unsigned char *>(l.out_goom);
     a.out_goom_last_only = l.out_goom_last_only;
     a.out_fact_steps = static_cast<unsigned char *>(l.out_fact_steps);

@@ -49,6 +49,8 @@ struct ChainArgs {
     int left_fact_cols; // padded columns of factored left factors
     int bias_mode; // 0 none, 1 GOOM vectors [batch, steps, d], 2 column d of the factored left factor
     int bias_col;  // state column that receives the bias
+    long long init_group;   // > 0: factored initial states come from a grouped carry array, (init_group + 1)
+    long long init_ngroups; //      entries per group of init_group chunks, init_ngroups groups per batch item
     const unsigned char *bias;
 };
 
@@ -62,12 +64,49 @@ template <> struct Comp<float> {
     __device__ static float log2_abs(float x) { return ::log2f(__builtin_fabsf(x)); }
     __device__ static float ldexp_(float x, int e) { return __builtin_ldexpf(x, e); }
     __device__ static int frexp_exp(float x) { int e; (void)__builtin_frexpf(x, &e); return e; }
-    __device__ static float inv_pi() { return 0.318309886183790671538f; }
     __device__ static float abs_(float x) { return __builtin_fabsf(x); }
+    __device__ static float ceil_(float x) { return __builtin_ceilf(x); }
+    __device__ static float neg_inf() { return -__builtin_huge_valf(); }
     // accumulator register v of lane group g holds row 4 g + v of the 16 x 16 tile
     __device__ static int row_of(int g, int v) { return 4 * g + v; }
     // position of logical index j inside LDS rows / the row-shift array
     __device__ static int phys(int j) { return j; }
+    // negative iff im is an odd multiple of pi
+    __device__ static bool is_negative(float im)
+    {
+        int k = (int)__builtin_rintf(im * 0.318309886183790671538f);
+        return (k & 1) != 0;
+    }
+    // row shift for a row whose largest log-magnitude is r: a whole number near r log2(e)
+    __device__ static float row_shift(float r) { return r > neg_inf() ? __builtin_ceilf(r * 1.44269504088896340736f) : 0.0f; }
+    // 2^(re log2(e) - n) for a whole number n >= re log2(e) (about): the product with
+    // log2(e) is carried in two floats, the whole part of the exponent is applied with
+    // ldexp, so the result is good to a few units in the last place for any shift.
+    __device__ static float exp2_shifted(float re, float n)
+    {
+#pragma clang fp contract(off) // p_hi must stay a rounded product: p_lo is its rounding error
+        const float kHi = 1.44269502162933349609375f;  // float nearest log2(e)
+        const float kLo = 1.925963033500011e-8f;       // log2(e) - kHi
+        float p_hi = re * kHi;
+        float p_lo = __builtin_fmaf(re, kHi, -p_hi);
+        p_lo = __builtin_fmaf(re, kLo, p_lo);
+        float t_hi = p_hi - n;
+        float k = __builtin_rintf(t_hi);
+        float f = (t_hi - k) + p_lo;
+        float y = __builtin_ldexpf(__builtin_amdgcn_exp2f(f), (int)k);
+        return t_hi > -160.0f ? y : 0.0f; // false for -inf and NaN as well: they become zero
+    }
+    // log-magnitude (natural log) of x 2^(n + e), rounded to the component type; x = 0 -> -inf
+    __device__ static float out_re(float x, float n, double e)
+    {
+#pragma clang fp contract(off)
+        const float kLn2Hi = 0.693147182464599609375f; // float nearest ln 2
+        const float kLn2Lo = -1.90465429995776806e-9f; // ln 2 - kLn2Hi
+        // scaling by 2^32 keeps subnormal x inside the hardware logarithm's domain
+        float l2 = __builtin_amdgcn_logf(__builtin_fabsf(x) * 4294967296.0f) - 32.0f;
+        float s = n + (float)e;
+        return __builtin_fmaf(s, kLn2Hi, __builtin_fmaf(s, kLn2Lo, l2 * kLn2Hi));
+    }
 };
 template <> struct Comp<double> {
     typedef d4 vec4;
@@ -78,31 +117,42 @@ template <> struct Comp<double> {
     __device__ static double log2_abs(double x) { return ::log2(__builtin_fabs(x)); }
     __device__ static double ldexp_(double x, int e) { return __builtin_ldexp(x, e); }
     __device__ static int frexp_exp(double x) { int e; (void)__builtin_frexp(x, &e); return e; }
-    __device__ static double inv_pi() { return 0.318309886183790671538; }
     __device__ static double abs_(double x) { return __builtin_fabs(x); }
+    __device__ static double ceil_(double x) { return __builtin_ceil(x); }
+    __device__ static double neg_inf() { return -__builtin_huge_val(); }
     // the double-precision instruction interleaves rows: register v of lane group g holds row 4 v + g
     __device__ static int row_of(int g, int v) { return 4 * v + g; }
     // ... so contraction index 16 kt + 4 v + g is stored at position 16 kt + 4 g + v, which
     // keeps the four values a lane needs contiguous
     __device__ static int phys(int j) { return (j & ~15) | ((j & 3) << 2) | ((j >> 2) & 3); }
+    __device__ static bool is_negative(double im)
+    {
+        long long k = (long long)__builtin_rint(im * 0.318309886183790671538);
+        return (k & 1LL) != 0;
+    }
+    __device__ static double row_shift(double r) { return r > neg_inf() ? __builtin_ceil(r * kLog2e) : 0.0; }
+    __device__ static double exp2_shifted(double re, double n)
+    {
+        double t = __builtin_fma(re, kLog2e, -n);
+        double k = __builtin_rint(t);
+        double y = __builtin_ldexp(::exp2(t - k), (int)(k > -4000.0 ? k : -4000.0));
+        return t > -1200.0 ? y : 0.0;
+    }
+    __device__ static double out_re(double x, double n, double e)
+    {
+        return x != 0.0 ? (::log2(__builtin_fabs(x)) + n + e) * kLn2 : neg_inf();
+    }
 };
 
-// 2^(t) for a double exponent t <= ~0 (t = -inf allowed): split into integer and
-// fraction in double so the fraction is exact, then one hardware exp2 and an ldexp.
-template <typename R> __device__ inline R exp2_shifted(double t)
+// 2^t for a double exponent t (t = -inf allowed), used off the hot path (initial states,
+// bias terms): whole and fractional part are split in double, so the fraction is exact.
+template <typename R> __device__ inline R exp2_of(double t)
 {
     t = t > -4000.0 ? t : -4000.0; // also maps -inf and NaN to "underflows to zero"
     t = t < 4000.0 ? t : 4000.0;
     double k = __builtin_rint(t);
     R f = (R)(t - k);
     return Comp<R>::ldexp_(Comp<R>::exp2_frac(f), (int)k);
-}
-
-// sign carried by the imaginary part: negative iff im is an odd multiple of pi
-template <typename R> __device__ inline bool is_negative(R im)
-{
-    int k = (int)__builtin_rint((double)(im * Comp<R>::inv_pi()));
-    return (k & 1) != 0;
 }
 
 template <typename R> __device__ inline R wave_xor_max(R v, int mask)
@@ -118,25 +168,34 @@ template <typename R> struct Item {
     R re0, im0, re1, im1;
 };
 
+// Register budget: waves per SIMD the compiler must leave room for.  The 64 x 64 float
+// kernel keeps 16 state + 16 accumulator + 32 prefetch registers per lane and fits in a
+// quarter of the register file, so four workgroups share a compute unit.
+constexpr int waves_per_simd(int comp_bytes, int dp, int nw)
+{
+    return (comp_bytes == 4 && dp <= 64 && nw >= dp / 16) ? 2 : (comp_bytes == 4 && dp <= 64) ? 2 : 1;
+}
+
 template <typename R, int DP, int NW, int LEFT_FACT>
-__global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
+__global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void chain_kernel(ChainArgs a)
 {
     constexpr int KT = DP / 16;
     constexpr int LPR = DP / 2; // producer lanes per row
     constexpr int NT = NW * 64;
     constexpr int LDA = DP + Comp<R>::kPad;
     constexpr int NITEMS = DP * LPR;
-    constexpr int Q = (NITEMS + NT - 1) / NT; // items per thread
-    constexpr int QB = Q < 8 ? Q : 8;         // items loaded ahead per batch
+    constexpr int Q = (NITEMS + NT - 1) / NT;  // items per thread
+    constexpr bool PREFETCH = Q <= 16;         // items of the next factor wait in registers during the product
+    constexpr int QB = PREFETCH ? Q : 8;       // items per batch
     typedef typename Comp<R>::vec4 vec4;
 
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr size_t kTileBytes = (size_t)DP * LDA * sizeof(R);
     constexpr size_t kBufBytes = kTileBytes + (size_t)DP * sizeof(double);
     constexpr int NBUF = (2 * kBufBytes + 64 <= 160 * 1024) ? 2 : 1; // double buffer when it fits in LDS
-    // buffer b: tile at smem + b * kBufBytes, row shifts (double) after the tile
+    // buffer b: tile at smem + b * kBufBytes, row shifts after the tile
     auto tile_of = [&](int b) { return reinterpret_cast<R *>(smem + (size_t)b * kBufBytes); };
-    auto nsh_of = [&](int b) { return reinterpret_cast<double *>(smem + (size_t)b * kBufBytes + kTileBytes); };
+    auto nsh_of = [&](int b) { return reinterpret_cast<R *>(smem + (size_t)b * kBufBytes + kTileBytes); };
     double *wave_red = reinterpret_cast<double *>(smem + NBUF * kBufBytes); // NW doubles
 
     const int tid = threadIdx.x;
@@ -147,6 +206,7 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
     const int n_rows = a.n, d = a.d, m = a.m;
     const int col = wave * 16 + c;
     const bool slab_active = wave < a.nslabs;
+    const R kNegInf = Comp<R>::neg_inf();
 
     const long long chain = blockIdx.x;
     const long long item = chain / a.chunks_launched;
@@ -157,82 +217,91 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
     const long long chain_global = item * a.chunks_per_item + chunk; // index into per-chain arrays
 
     const unsigned char *left0 = a.left + item * a.left_batch_stride + t0 * a.left_step_stride;
+    const bool vec_ok = (d % 2) == 0;
 
     // ------------------------------------------------------------------ producer
-    // Exponentiate left factor number t into LDS buffer buf:
-    //   tile[i][j] = (+-) 2^(log2|A_ij| - n_i),  n_i = ceil(max_j log2|A_ij|)  (0 for a zero row)
-    // and record n_i.  Rows/columns beyond d are zero.
-    auto produce = [&](long long t, int buf) {
-        R *tile = tile_of(buf);
-        double *nsh = nsh_of(buf);
+    // Left factor number t is turned into an LDS tile
+    //   tile[i][j] = (+-) 2^(log2|A_ij| - n_i),  n_i = a whole number near max_j log2|A_ij|
+    // (0 for a zero row), with n_i recorded beside it.  Rows and columns beyond the
+    // factor's size are zero.  load_items reads batch q0 of the factor into registers,
+    // convert_items exponentiates it into the tile.
+    auto load_items = [&](long long t, int q0, Item<R> (&it)[QB]) {
         const unsigned char *src = left0 + t * a.left_step_stride;
 #pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            const int p = tid + (q0 + q) * NT;
+            const int row = p / LPR, cj = 2 * (p % LPR);
+            const bool v0 = (p < NITEMS) && row < n_rows && cj < d;
+            const bool v1 = v0 && (cj + 1 < d);
+            if (LEFT_FACT) {
+                // factored left factor: mantissas [DP][left_fact_cols], leading columns on one exponent
+                const R *mp = reinterpret_cast<const R *>(src) + (size_t)row * a.left_fact_cols + cj;
+                it[q].re0 = v0 ? mp[0] : (R)0;
+                it[q].re1 = v1 ? mp[1] : (R)0;
+                it[q].im0 = it[q].im1 = (R)0;
+            } else {
+                const R *gp = reinterpret_cast<const R *>(src) + ((size_t)row * d + cj) * 2;
+                if (v1 && vec_ok) {
+                    if (sizeof(R) == 4) {
+                        const f4 w = *reinterpret_cast<const f4 *>(gp);
+                        it[q].re0 = w[0]; it[q].im0 = w[1]; it[q].re1 = w[2]; it[q].im1 = w[3];
+                    } else {
+                        const d4 w = *reinterpret_cast<const d4 *>(gp);
+                        it[q].re0 = w[0]; it[q].im0 = w[1]; it[q].re1 = w[2]; it[q].im1 = w[3];
+                    }
+                } else {
+                    it[q].re0 = v0 ? gp[0] : kNegInf; it[q].im0 = v0 ? gp[1] : (R)0;
+                    it[q].re1 = v1 ? gp[2] : kNegInf; it[q].im1 = v1 ? gp[3] : (R)0;
+                }
+            }
+        }
+    };
+    auto convert_items = [&](long long t, int q0, const Item<R> (&it)[QB], int buf) {
+        R *tile = tile_of(buf);
+        R *nsh = nsh_of(buf);
+        R common = (R)0;
+        if (LEFT_FACT) {
+            const unsigned char *src = left0 + t * a.left_step_stride;
+            common = (R) * reinterpret_cast<const double *>(src + (size_t)DP * a.left_fact_cols * sizeof(R));
+        }
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            const int p = tid + (q0 + q) * NT;
+            const int row = p / LPR, cp = p % LPR, cj = 2 * cp;
+            R x0, x1, n;
+            if (LEFT_FACT) {
+                const R a0 = Comp<R>::abs_(it[q].re0), a1 = Comp<R>::abs_(it[q].re1);
+                R r = a0 > a1 ? a0 : a1;
+#pragma unroll
+                for (int s = 1; s < LPR; s <<= 1) r = wave_xor_max<R>(r, s);
+                const int e = (r > (R)0 && r < -kNegInf) ? Comp<R>::frexp_exp(r) : 0;
+                x0 = Comp<R>::ldexp_(it[q].re0, -e);
+                x1 = Comp<R>::ldexp_(it[q].re1, -e);
+                n = (R)e + common;
+            } else {
+                R r = it[q].re0 > it[q].re1 ? it[q].re0 : it[q].re1;
+#pragma unroll
+                for (int s = 1; s < LPR; s <<= 1) r = wave_xor_max<R>(r, s);
+                n = Comp<R>::row_shift(r);
+                x0 = Comp<R>::exp2_shifted(it[q].re0, n);
+                x1 = Comp<R>::exp2_shifted(it[q].re1, n);
+                if (Comp<R>::is_negative(it[q].im0)) x0 = -x0;
+                if (Comp<R>::is_negative(it[q].im1)) x1 = -x1;
+            }
+            if (p < NITEMS) {
+                tile[row * LDA + Comp<R>::phys(cj)] = x0;
+                tile[row * LDA + Comp<R>::phys(cj + 1)] = x1;
+                if (cp == 0) nsh[Comp<R>::phys(row)] = n;
+            }
+        }
+    };
+    // whole factor, no registers kept (start-up, and factors too large to prefetch)
+    auto produce_now = [&](long long t, int buf) {
+#pragma unroll 1
         for (int q0 = 0; q0 < Q; q0 += QB) {
             Item<R> it[QB];
-            double common = 0.0;
-#pragma unroll
-            for (int q = 0; q < QB; ++q) {
-                int p = tid + (q0 + q) * NT;
-                int row = p / LPR, cp = p % LPR, cj = 2 * cp;
-                bool v0 = (p < NITEMS) && row < n_rows && cj < d;
-                bool v1 = v0 && (cj + 1 < d);
-                if (LEFT_FACT) {
-                    // factored left factor: mantissas [DP][fact_cols], all columns on one exponent
-                    const R *mp = reinterpret_cast<const R *>(src) + (size_t)row * a.left_fact_cols + cj;
-                    it[q].re0 = v0 ? mp[0] : (R)0;
-                    it[q].re1 = v1 ? mp[1] : (R)0;
-                    it[q].im0 = it[q].im1 = (R)0;
-                } else {
-                    const R *gp = reinterpret_cast<const R *>(src) + ((size_t)row * d + cj) * 2;
-                    R ninf = -__builtin_huge_val();
-                    if (v1 && (d % 2 == 0)) {
-                        if (sizeof(R) == 4) {
-                            f4 w = *reinterpret_cast<const f4 *>(gp);
-                            it[q].re0 = w[0]; it[q].im0 = w[1]; it[q].re1 = w[2]; it[q].im1 = w[3];
-                        } else {
-                            it[q].re0 = gp[0]; it[q].im0 = gp[1]; it[q].re1 = gp[2]; it[q].im1 = gp[3];
-                        }
-                    } else {
-                        it[q].re0 = v0 ? gp[0] : ninf; it[q].im0 = v0 ? gp[1] : (R)0;
-                        it[q].re1 = v1 ? gp[2] : ninf; it[q].im1 = v1 ? gp[3] : (R)0;
-                    }
-                }
-            }
-            if (LEFT_FACT) {
-                const double *ex = reinterpret_cast<const double *>(src + (size_t)DP * a.left_fact_cols * sizeof(R));
-                common = ex[0];
-            }
-#pragma unroll
-            for (int q = 0; q < QB; ++q) {
-                int p = tid + (q0 + q) * NT;
-                int row = p / LPR, cp = p % LPR, cj = 2 * cp;
-                R x0, x1;
-                double n;
-                if (LEFT_FACT) {
-                    R a0 = Comp<R>::abs_(it[q].re0), a1 = Comp<R>::abs_(it[q].re1);
-                    R r = a0 > a1 ? a0 : a1;
-#pragma unroll
-                    for (int s = 1; s < LPR; s <<= 1) r = wave_xor_max<R>(r, s);
-                    int e = (r > (R)0 && r < (R)__builtin_huge_val()) ? Comp<R>::frexp_exp(r) : 0;
-                    x0 = Comp<R>::ldexp_(it[q].re0, -e);
-                    x1 = Comp<R>::ldexp_(it[q].re1, -e);
-                    n = (double)e + common;
-                } else {
-                    R r = it[q].re0 > it[q].re1 ? it[q].re0 : it[q].re1;
-#pragma unroll
-                    for (int s = 1; s < LPR; s <<= 1) r = wave_xor_max<R>(r, s);
-                    n = (r > -(R)__builtin_huge_val()) ? __builtin_ceil((double)r * kLog2e) : 0.0;
-                    x0 = exp2_shifted<R>(__builtin_fma((double)it[q].re0, kLog2e, -n));
-                    x1 = exp2_shifted<R>(__builtin_fma((double)it[q].re1, kLog2e, -n));
-                    if (is_negative<R>(it[q].im0)) x0 = -x0;
-                    if (is_negative<R>(it[q].im1)) x1 = -x1;
-                }
-                if (p < NITEMS) {
-                    tile[row * LDA + Comp<R>::phys(cj)] = x0;
-                    tile[row * LDA + Comp<R>::phys(cj + 1)] = x1;
-                    if (cp == 0) nsh[Comp<R>::phys(row)] = n;
-                }
-            }
+            load_items(t, q0, it);
+            convert_items(t, q0, it, buf);
         }
     };
 
@@ -249,7 +318,13 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
                 st[kt][v] = (a.init_mode == 0 && row == col && row < d && col < m) ? (R)1 : (R)0;
             }
     } else if (a.init_mode == 1) {
-        const unsigned char *ip = a.init + chain_global * a.init_stride;
+        long long iidx = chain_global;
+        if (a.init_group > 0) { // chunk c sits in group min(c / S, G - 1) at offset c - group * S
+            long long grp = chunk / a.init_group;
+            if (grp >= a.init_ngroups) grp = a.init_ngroups - 1;
+            iidx = (item * a.init_ngroups + grp) * (a.init_group + 1) + (chunk - grp * a.init_group);
+        }
+        const unsigned char *ip = a.init + iidx * a.init_stride;
         const R *mp = reinterpret_cast<const R *>(ip);
         const double *ep = reinterpret_cast<const double *>(ip + fact_mant_bytes);
 #pragma unroll
@@ -261,27 +336,29 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
     } else {
         // GOOM initial state [d, m]: column shift e = ceil(max_i log2|x_ik|), W = +-2^(log2|x| - e)
         const R *gp = reinterpret_cast<const R *>(a.init + item * a.init_stride);
-        R re[KT][4], im[KT][4];
-        R cmax = -(R)__builtin_huge_val();
+        R cmax = kNegInf;
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                int row = 16 * kt + Comp<R>::row_of(g, v);
-                bool ok = slab_active && row < d && col < m;
-                re[kt][v] = ok ? gp[((size_t)row * m + col) * 2] : -(R)__builtin_huge_val();
-                im[kt][v] = ok ? gp[((size_t)row * m + col) * 2 + 1] : (R)0;
-                cmax = re[kt][v] > cmax ? re[kt][v] : cmax;
+                const int row = 16 * kt + Comp<R>::row_of(g, v);
+                const bool ok = slab_active && row < d && col < m;
+                const R re = ok ? gp[((size_t)row * m + col) * 2] : kNegInf;
+                cmax = re > cmax ? re : cmax;
             }
         cmax = wave_xor_max<R>(cmax, 16);
         cmax = wave_xor_max<R>(cmax, 32);
-        ecol = (cmax > -(R)__builtin_huge_val()) ? __builtin_ceil((double)cmax * kLog2e) : 0.0;
+        ecol = (cmax > kNegInf) ? __builtin_ceil((double)cmax * kLog2e) : 0.0;
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                R x = exp2_shifted<R>(__builtin_fma((double)re[kt][v], kLog2e, -ecol));
-                st[kt][v] = is_negative<R>(im[kt][v]) ? -x : x;
+                const int row = 16 * kt + Comp<R>::row_of(g, v);
+                const bool ok = slab_active && row < d && col < m;
+                const R re = ok ? gp[((size_t)row * m + col) * 2] : kNegInf;
+                const R im = ok ? gp[((size_t)row * m + col) * 2 + 1] : (R)0;
+                const R x = exp2_of<R>(__builtin_fma((double)re, kLog2e, -ecol));
+                st[kt][v] = Comp<R>::is_negative(im) ? -x : x;
             }
     }
 
@@ -335,13 +412,15 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
 
     unsigned char *fact_steps = a.out_fact_steps ? a.out_fact_steps + (chain_global * (a.chunk_len + 1)) * a.fact_stride : nullptr;
 
-    if (len > 0) produce(0, 0);
+    Item<R> pre[QB]; // the next left factor, on its way from memory while the current product runs
+    if (len > 0) produce_now(0, 0);
+    if (PREFETCH && len > 1) load_items(1, 0, pre);
     __syncthreads();
 
     for (long long t = 0; t < len; ++t) {
         const int cur = NBUF == 2 ? (int)(t & 1) : 0;
         const R *tile = tile_of(cur);
-        const double *nsh = nsh_of(cur);
+        const R *nsh = nsh_of(cur);
 
         if (fact_steps) store_fact(fact_steps + t * a.fact_stride, false);
 
@@ -364,8 +443,11 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
         }
 
         // ------------------------------------------------------------ epilogue
-        // acc[mt][v] is entry (i = 16 mt + 4 g + v, col) of the scaled product; the true
-        // value is acc * 2^(n_i + ecol).
+        // acc[mt][v] is entry (i = 16 mt + row_of(g, v), col) of the scaled product; the
+        // true value is acc * 2^(n_i + ecol).  Exponent arithmetic runs in the component
+        // type on whole numbers: differences that matter are between numbers of like size
+        // and therefore exact; a reference exponent that is a few units off only moves the
+        // mantissas' scale, never the represented value.
         //
         // bias column (linear recurrence with bias): b_i, given as a GOOM or as a column
         // of the factored left factor, is added to entry (i, bias_col) in the log2 domain.
@@ -377,8 +459,8 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
             if (a.bias_mode == 1) {
                 const R *bp = reinterpret_cast<const R *>(a.bias) + ((size_t)(item * a.steps + t0 + t) * n_rows + i) * 2;
                 R br = bp[0];
-                if (br > -(R)__builtin_huge_val()) blog = (double)br * kLog2e - ecol;
-                bneg = is_negative<R>(bp[1]);
+                if (br > kNegInf) blog = (double)br * kLog2e - ecol;
+                bneg = Comp<R>::is_negative(bp[1]);
             } else {
                 const unsigned char *src = left0 + t * a.left_step_stride;
                 const R *mp = reinterpret_cast<const R *>(src);
@@ -389,15 +471,15 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
             }
         };
 
-        // column reference: cm = max_i log2 of the entries in units of 2^ecol
-        double cm = kNegBig;
+        // column reference: cm = max_i of (binary exponent of the entry) + n_i
+        R cm = kNegInf;
 #pragma unroll
         for (int mt = 0; mt < KT; ++mt) {
-            const d4 nv = *reinterpret_cast<const d4 *>(&nsh[16 * mt + 4 * g]);
+            const vec4 nv = *reinterpret_cast<const vec4 *>(&nsh[16 * mt + 4 * g]);
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                R x = acc[mt][v];
-                double lg = (x != (R)0) ? (double)Comp<R>::frexp_exp(x) + nv[v] : kNegBig;
+                const R x = acc[mt][v];
+                const R lg = (x != (R)0) ? (R)Comp<R>::frexp_exp(x) + nv[v] : kNegInf;
                 cm = lg > cm ? lg : cm;
             }
         }
@@ -409,17 +491,15 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
                     double blog;
                     bool bneg;
                     bias_term(16 * mt + Comp<R>::row_of(g, v), blog, bneg);
-                    cm = blog > cm ? blog : cm;
+                    const R lb = blog > kNegBig ? (R)__builtin_ceil(blog) : kNegInf;
+                    cm = lb > cm ? lb : cm;
                 }
         }
-        {
-            double o = shfl_xor_double(cm, 16);
-            cm = o > cm ? o : cm;
-            o = shfl_xor_double(cm, 32);
-            cm = o > cm ? o : cm;
-        }
-        if (bias_lane && cm > kNegBig) cm = __builtin_ceil(cm) + 2.0; // whole exponent, room for the sum of two terms
-        const bool col_nonzero = cm > kNegBig;
+        cm = wave_xor_max<R>(cm, 16);
+        cm = wave_xor_max<R>(cm, 32);
+        if (bias_lane) cm += (R)2; // room for the sum of two terms
+        const bool col_nonzero = cm > kNegInf;
+        const R cms = col_nonzero ? cm : (R)0;
 
         const bool want_out = a.out_goom && slab_active && col < m && (!a.out_goom_last_only || t == len - 1);
         R *outp = nullptr;
@@ -431,16 +511,14 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
         if (!bias_lane) {
 #pragma unroll
             for (int mt = 0; mt < KT; ++mt) {
-                const d4 nv = *reinterpret_cast<const d4 *>(&nsh[16 * mt + 4 * g]);
+                const vec4 nv = *reinterpret_cast<const vec4 *>(&nsh[16 * mt + 4 * g]);
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int i = 16 * mt + Comp<R>::row_of(g, v);
-                    R x = acc[mt][v];
+                    const R x = acc[mt][v];
                     if (want_out && i < n_rows) {
-                        // log-magnitude of the true value: (log2|x| + n_i + ecol) ln 2, rounded once
-                        R re = (x != (R)0) ? (R)(((double)Comp<R>::log2_abs(x) + nv[v] + ecol) * kLn2)
-                                           : -(R)__builtin_huge_val();
-                        R im = x < (R)0 ? Comp<R>::pi() : (R)0;
+                        const R re = Comp<R>::out_re(x, nv[v], ecol);
+                        const R im = x < (R)0 ? Comp<R>::pi() : (R)0;
                         R *o = outp + ((size_t)i * m + col) * 2;
                         if (sizeof(R) == 4) {
                             *reinterpret_cast<float2 *>(o) = float2{(float)re, (float)im};
@@ -448,32 +526,33 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
                             *reinterpret_cast<double2 *>(o) = double2{(double)re, (double)im};
                         }
                     }
-                    double sh = nv[v] - cm;
-                    sh = sh > -4000.0 ? sh : -4000.0;
-                    st[mt][v] = col_nonzero ? Comp<R>::ldexp_(x, (int)sh) : (R)0;
+                    R sh = nv[v] - cms;
+                    sh = sh > (R)-4000 ? sh : (R)-4000;
+                    sh = sh < (R)4000 ? sh : (R)4000;
+                    st[mt][v] = Comp<R>::ldexp_(x, (int)sh);
                 }
             }
         } else {
 #pragma unroll
             for (int mt = 0; mt < KT; ++mt) {
-                const d4 nv = *reinterpret_cast<const d4 *>(&nsh[16 * mt + 4 * g]);
+                const vec4 nv = *reinterpret_cast<const vec4 *>(&nsh[16 * mt + 4 * g]);
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int i = 16 * mt + Comp<R>::row_of(g, v);
-                    R x = acc[mt][v];
+                    const R x = acc[mt][v];
                     double blog;
                     bool bneg;
                     bias_term(i, blog, bneg);
                     // entry = x 2^(n_i - cm) + (+-) 2^(blog - cm), in units of 2^(ecol + cm)
-                    double sh = nv[v] - cm;
-                    sh = sh > -4000.0 ? sh : -4000.0;
-                    R xa = col_nonzero ? Comp<R>::ldexp_(x, (int)sh) : (R)0;
-                    R xb = (col_nonzero && blog > kNegBig) ? exp2_shifted<R>(blog - cm) : (R)0;
-                    R xs = xa + (bneg ? -xb : xb);
+                    R sh = nv[v] - cms;
+                    sh = sh > (R)-4000 ? sh : (R)-4000;
+                    sh = sh < (R)4000 ? sh : (R)4000;
+                    const R xa = Comp<R>::ldexp_(x, (int)sh);
+                    const R xb = (col_nonzero && blog > kNegBig) ? exp2_of<R>(blog - (double)cm) : (R)0;
+                    const R xs = xa + (bneg ? -xb : xb);
                     if (want_out && i < n_rows) {
-                        R re = (xs != (R)0) ? (R)(((double)Comp<R>::log2_abs(xs) + cm + ecol) * kLn2)
-                                            : -(R)__builtin_huge_val();
-                        R im = xs < (R)0 ? Comp<R>::pi() : (R)0;
+                        const R re = Comp<R>::out_re(xs, cms, ecol);
+                        const R im = xs < (R)0 ? Comp<R>::pi() : (R)0;
                         R *o = outp + ((size_t)i * m + col) * 2;
                         o[0] = re;
                         o[1] = im;
@@ -482,11 +561,19 @@ __global__ __launch_bounds__(NW * 64) void chain_kernel(ChainArgs a)
                 }
             }
         }
-        if (col_nonzero) ecol += cm;
+        if (col_nonzero) ecol += (double)cm;
 
         // ------------------------------------------------------------ next left factor
         if (NBUF == 1) __syncthreads(); // every wave is done reading the only tile
-        if (t + 1 < len) produce(t + 1, NBUF == 2 ? (cur ^ 1) : 0);
+        if (t + 1 < len) {
+            const int nxt = NBUF == 2 ? (cur ^ 1) : 0;
+            if (PREFETCH) {
+                convert_items(t + 1, 0, pre, nxt);
+                if (t + 2 < len) load_items(t + 2, 0, pre);
+            } else {
+                produce_now(t + 1, nxt);
+            }
+        }
         __syncthreads();
     }
 

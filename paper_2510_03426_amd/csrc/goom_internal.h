@@ -69,6 +69,8 @@ struct ChainLaunch {
     int init_mode;        // 0 identity, 1 factored, 2 GOOM, 3 zero
     const void *init;     // per chain (factored) or per batch item (GOOM)
     long long init_stride;       // bytes between consecutive chains (factored) / batch items (GOOM)
+    long long init_group;        // > 0: factored initial states come from a grouped carry array (see goom_api.hip)
+    long long init_ngroups;
     void *out_goom;       // NULL or GOOM outputs, [batch, steps, d, m]
     int out_goom_last_only;      // 1: out_goom is [batch(, chunk), d, m], written at each chain's last step
     void *out_fact_steps; // NULL or factored state before each step and after the last: (len + 1) per chain
