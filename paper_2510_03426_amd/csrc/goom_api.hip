@@ -91,24 +91,51 @@ static long long default_chunk_len(long long T, long long batch, long long reque
     return L < 1 ? 1 : L;
 }
 
+// Layout of one scan in the workspace.
+//   totals  : product of every chunk, [batch][C] factored matrices of m_tot columns
+//   carries : the prefix that enters every chunk, factored matrices of m_state columns
+// The carries are the prefixes of the chunk products, which is a scan again.  With few
+// chunks one workgroup per batch item walks them in order.  With many, the same three
+// steps are applied once more: chunk products are multiplied down in groups of S (group
+// products), one chain walks the G group products, and every group is then re-walked
+// from its incoming prefix.  Serial depth falls from C to about 2 S + G steps.  Carries
+// of a grouped scan are stored per group with S + 1 entries (the last one repeats the
+// first of the next group).
 struct ScanPlan {
-    long long L, C;
+    long long L, C;  // chunk length, chunks per batch item
+    long long nt;    // chunk products the carry phase walks (C - 1 for a scan, C for a reduction)
+    long long S, G;  // group size and group count of the carry phase (S = 0: not grouped)
     int dp;
     FactLayout tot, car;
-    size_t tot_bytes, car_bytes;
+    size_t tot_bytes, car_bytes, gtot_bytes, gcar_bytes;
+    size_t total() const { return tot_bytes + car_bytes + gtot_bytes + gcar_bytes; }
 };
 
 static ScanPlan plan_scan(long long T, int d, int m_tot, int m_state, long long batch, int dtype,
-                          long long requested_chunk)
+                          long long requested_chunk, bool final_only)
 {
     ScanPlan p;
     p.L = default_chunk_len(T, batch, requested_chunk);
     p.C = (T + p.L - 1) / p.L;
+    p.nt = final_only ? p.C : p.C - 1;
     p.dp = padded_dim(d);
     p.tot = fact_layout(p.dp, m_tot, dtype);
     p.car = fact_layout(p.dp, m_state, dtype);
+    p.S = 0;
+    p.G = 0;
+    if (p.nt > 96) {
+        p.S = (long long)std::ceil(std::sqrt((double)p.nt));
+        p.G = (p.nt + p.S - 1) / p.S;
+    }
     p.tot_bytes = p.C > 1 ? (size_t)batch * p.C * p.tot.stride : 0;
-    p.car_bytes = p.C > 1 ? (size_t)batch * p.C * p.car.stride : 0;
+    p.gtot_bytes = p.S ? (size_t)batch * p.G * p.tot.stride : 0;
+    p.gcar_bytes = p.S ? (size_t)batch * p.G * p.car.stride : 0;
+    if (p.C <= 1 || final_only)
+        p.car_bytes = 0;
+    else if (p.S)
+        p.car_bytes = (size_t)batch * p.G * (p.S + 1) * p.car.stride;
+    else
+        p.car_bytes = (size_t)batch * p.C * p.car.stride;
     return p;
 }
 
@@ -122,7 +149,6 @@ static int check_scan_args(goom_ctx *ctx, const void *M, const void *out, long l
     if (opts && opts->flags != 0) return fail(ctx, GOOM_EINVAL, "unknown scan flags 0x%x", opts->flags);
     if (opts && opts->chunk_len < 0) return fail(ctx, GOOM_EINVAL, "negative chunk_len");
     if (!aligned(M, 16) || !aligned(out, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
-    if ((d % 2) != 0 && dtype == GOOM_C64 && d != 1) { /* odd row lengths take the element-wise load path */ }
     return GOOM_OK;
 }
 
@@ -135,6 +161,116 @@ static int check_workspace(goom_ctx *ctx, const void *ws, size_t have, size_t ne
     return GOOM_OK;
 }
 
+// What the carry phase needs to know about the state it carries.
+struct CarryState {
+    int m;                 // columns of the carried state
+    int init_mode;         // 0 identity, 2 GOOM, 3 zero
+    const void *init;      // GOOM initial state per batch item (init_mode 2)
+    long long init_stride;
+    bool bias;             // chunk products are augmented [A | b]: carry a vector, add b
+    void *final_goom;      // reduction: the last prefix as GOOMs, [batch, d, m]
+};
+
+// Phase 2: prefixes of the chunk products.  On return (for a scan) `carries` holds the
+// prefix entering every chunk, indexed as described at ScanPlan.
+static int carry_phase(goom_ctx *ctx, const ScanPlan &p, int dtype, int d, long long batch, unsigned char *totals,
+                       unsigned char *carries, unsigned char *gtot, unsigned char *gcar, const CarryState &cs,
+                       const char *label)
+{
+    ChainLaunch base;
+    std::memset(&base, 0, sizeof base);
+    base.dtype = dtype;
+    base.n = d;
+    base.d = d;
+    base.batch = batch;
+    base.left_fact = 1;
+    base.left_fact_cols = p.tot.cols_padded;
+    base.left_step_stride = (long long)p.tot.stride;
+    base.label = label;
+
+    if (!p.S) { // one chain per batch item over all chunk products
+        ChainLaunch l = base;
+        l.m = cs.m;
+        l.left = totals;
+        l.left_batch_stride = (long long)p.C * p.tot.stride;
+        l.steps = p.nt;
+        l.chunk_len = p.nt;
+        l.chunks_launched = 1;
+        l.init_mode = cs.init_mode;
+        l.init = cs.init;
+        l.init_stride = cs.init_stride;
+        l.bias_mode = cs.bias ? 2 : 0;
+        l.bias_col = 0;
+        if (cs.final_goom) {
+            l.out_goom = cs.final_goom;
+            l.out_goom_last_only = 1;
+        } else {
+            l.out_fact_steps = carries;
+            l.fact_stride = (long long)p.car.stride;
+            l.fact_cols = p.car.cols_padded;
+        }
+        return launch_chain(ctx, l);
+    }
+    { // group products (the last group's is needed only by the reduction)
+        ChainLaunch l = base;
+        l.m = cs.bias ? d + 1 : d;
+        l.left = totals;
+        l.left_batch_stride = (long long)p.C * p.tot.stride;
+        l.steps = p.nt;
+        l.chunk_len = p.S;
+        l.chunks_launched = cs.final_goom ? p.G : p.G - 1;
+        l.init_mode = 0;
+        l.bias_mode = cs.bias ? 2 : 0;
+        l.bias_col = d;
+        l.out_fact_final = gtot;
+        l.final_common_exponent = 1;
+        l.fact_stride = (long long)p.tot.stride;
+        l.fact_cols = p.tot.cols_padded;
+        if (int s = launch_chain(ctx, l)) return s;
+    }
+    { // prefixes of the group products
+        ChainLaunch l = base;
+        l.m = cs.m;
+        l.left = gtot;
+        l.left_batch_stride = (long long)p.G * p.tot.stride;
+        l.steps = cs.final_goom ? p.G : p.G - 1;
+        l.chunk_len = l.steps;
+        l.chunks_launched = 1;
+        l.init_mode = cs.init_mode;
+        l.init = cs.init;
+        l.init_stride = cs.init_stride;
+        l.bias_mode = cs.bias ? 2 : 0;
+        l.bias_col = 0;
+        if (cs.final_goom) {
+            l.out_goom = cs.final_goom;
+            l.out_goom_last_only = 1;
+            return launch_chain(ctx, l);
+        }
+        l.out_fact_steps = gcar;
+        l.fact_stride = (long long)p.car.stride;
+        l.fact_cols = p.car.cols_padded;
+        if (int s = launch_chain(ctx, l)) return s;
+    }
+    { // every group again, from its incoming prefix: the carries of its chunks
+        ChainLaunch l = base;
+        l.m = cs.m;
+        l.left = totals;
+        l.left_batch_stride = (long long)p.C * p.tot.stride;
+        l.steps = p.nt;
+        l.chunk_len = p.S;
+        l.chunks_launched = p.G;
+        l.init_mode = 1;
+        l.init = gcar;
+        l.init_stride = (long long)p.car.stride;
+        l.bias_mode = cs.bias ? 2 : 0;
+        l.bias_col = 0;
+        l.out_fact_steps = carries;
+        l.fact_stride = (long long)p.car.stride;
+        l.fact_cols = p.car.cols_padded;
+        return launch_chain(ctx, l);
+    }
+}
+
 // scan and reduce share one driver; `final_only` selects the reduction
 static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, long long T, int d, int m, long long batch,
                     int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes, bool final_only)
@@ -142,9 +278,8 @@ static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, lon
     if (int s = check_scan_args(ctx, M, P, T, d, m, batch, dtype, opts)) return s;
     if (!init && m != d) return fail(ctx, GOOM_EINVAL, "without an initial state the outputs are d x d (m=%d d=%d)", m, d);
     if (init && !aligned(init, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
-    const ScanPlan p = plan_scan(T, d, d, m, batch, dtype, opts ? opts->chunk_len : 0);
-    const size_t need = p.tot_bytes + (final_only ? 0 : p.car_bytes);
-    if (int s = check_workspace(ctx, ws, ws_bytes, need)) return s;
+    const ScanPlan p = plan_scan(T, d, d, m, batch, dtype, opts ? opts->chunk_len : 0, final_only);
+    if (int s = check_workspace(ctx, ws, ws_bytes, p.total())) return s;
     const size_t cb = 2 * comp_bytes(dtype);
     if (int s = need_ctx(ctx)) return s;
 
@@ -154,14 +289,14 @@ static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, lon
     base.n = d;
     base.d = d;
     base.batch = batch;
+    base.left = M;
+    base.left_batch_stride = (long long)T * d * d * cb;
+    base.left_step_stride = (long long)d * d * cb;
+    base.steps = T;
 
     if (p.C == 1) { // one chain per batch item walks everything
         ChainLaunch l = base;
         l.m = m;
-        l.left = M;
-        l.left_batch_stride = (long long)T * d * d * cb;
-        l.left_step_stride = (long long)d * d * cb;
-        l.steps = T;
         l.chunk_len = T;
         l.chunks_launched = 1;
         l.init_mode = init ? 2 : 0;
@@ -175,16 +310,14 @@ static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, lon
 
     unsigned char *totals = static_cast<unsigned char *>(ws);
     unsigned char *carries = totals + p.tot_bytes;
+    unsigned char *gtot = carries + p.car_bytes;
+    unsigned char *gcar = gtot + p.gtot_bytes;
 
     { // phase 1: product of every chunk (the last chunk's is needed only by the reduction)
         ChainLaunch l = base;
         l.m = d;
-        l.left = M;
-        l.left_batch_stride = (long long)T * d * d * cb;
-        l.left_step_stride = (long long)d * d * cb;
-        l.steps = T;
         l.chunk_len = p.L;
-        l.chunks_launched = final_only ? p.C : p.C - 1;
+        l.chunks_launched = p.nt;
         l.init_mode = 0;
         l.out_fact_final = totals;
         l.final_common_exponent = 1;
@@ -193,44 +326,27 @@ static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, lon
         l.label = "scan_phase1_chunk_products";
         if (int s = launch_chain(ctx, l)) return s;
     }
-    { // phase 2: prefixes of the chunk products (one chain per batch item)
-        ChainLaunch l = base;
-        l.m = m;
-        l.left_fact = 1;
-        l.left = totals;
-        l.left_batch_stride = (long long)p.C * p.tot.stride;
-        l.left_step_stride = (long long)p.tot.stride;
-        l.left_fact_cols = p.tot.cols_padded;
-        l.steps = final_only ? p.C : p.C - 1;
-        l.chunk_len = l.steps;
-        l.chunks_launched = 1;
-        l.init_mode = init ? 2 : 0;
-        l.init = init;
-        l.init_stride = (long long)d * m * cb;
-        if (final_only) {
-            l.out_goom = P;
-            l.out_goom_last_only = 1;
-        } else {
-            l.out_fact_steps = carries;
-            l.fact_stride = (long long)p.car.stride;
-            l.fact_cols = p.car.cols_padded;
-        }
-        l.label = "scan_phase2_carry_chain";
-        if (int s = launch_chain(ctx, l)) return s;
+    { // phase 2: prefixes of the chunk products
+        CarryState cs;
+        cs.m = m;
+        cs.init_mode = init ? 2 : 0;
+        cs.init = init;
+        cs.init_stride = (long long)d * m * cb;
+        cs.bias = false;
+        cs.final_goom = final_only ? P : nullptr;
+        if (int s = carry_phase(ctx, p, dtype, d, batch, totals, carries, gtot, gcar, cs, "scan_phase2_carries")) return s;
         if (final_only) return GOOM_OK;
     }
     { // phase 3: every chunk again, from its incoming prefix, writing all outputs
         ChainLaunch l = base;
         l.m = m;
-        l.left = M;
-        l.left_batch_stride = (long long)T * d * d * cb;
-        l.left_step_stride = (long long)d * d * cb;
-        l.steps = T;
         l.chunk_len = p.L;
         l.chunks_launched = p.C;
         l.init_mode = 1;
         l.init = carries;
         l.init_stride = (long long)p.car.stride;
+        l.init_group = p.S;
+        l.init_ngroups = p.G;
         l.fact_stride = (long long)p.car.stride;
         l.fact_cols = p.car.cols_padded;
         l.out_goom = P;
@@ -389,16 +505,16 @@ size_t goom_scan_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dty
 {
     if (T <= 0 || d <= 0 || m <= 0 || batch <= 0 || d > GOOM_MAX_DIM || m > GOOM_MAX_DIM) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
-    ScanPlan p = plan_scan(T, d, d, m, batch, dtype, opts ? opts->chunk_len : 0);
-    return p.tot_bytes + p.car_bytes;
+    ScanPlan p = plan_scan(T, d, d, m, batch, dtype, opts ? opts->chunk_len : 0, false);
+    return p.total();
 }
 
 size_t goom_reduce_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype, const goom_scan_opts *opts)
 {
     if (T <= 0 || d <= 0 || m <= 0 || batch <= 0 || d > GOOM_MAX_DIM || m > GOOM_MAX_DIM) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
-    ScanPlan p = plan_scan(T, d, d, m, batch, dtype, opts ? opts->chunk_len : 0);
-    return p.tot_bytes;
+    ScanPlan p = plan_scan(T, d, d, m, batch, dtype, opts ? opts->chunk_len : 0, true);
+    return p.total();
 }
 
 int goom_scan(goom_ctx *ctx, const void *M, const void *init, void *P, int64_t T, int d, int m, int64_t batch, int dtype,
@@ -417,8 +533,8 @@ size_t goom_affine_scan_workspace_bytes(int64_t T, int d, int64_t batch, int dty
 {
     if (T <= 0 || d <= 0 || batch <= 0 || d >= GOOM_MAX_DIM) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
-    ScanPlan p = plan_scan(T, d, d + 1, 1, batch, dtype, opts ? opts->chunk_len : 0);
-    return p.tot_bytes + p.car_bytes;
+    ScanPlan p = plan_scan(T, d, d + 1, 1, batch, dtype, opts ? opts->chunk_len : 0, false);
+    return p.total();
 }
 
 int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H, int64_t T, int d,
@@ -428,8 +544,8 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
     if (!bias) return fail(ctx, GOOM_EINVAL, "null data pointer");
     if (d >= GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "the recurrence with bias needs d < %d", GOOM_MAX_DIM);
     if (!aligned(bias, 16) || (h0 && !aligned(h0, 16))) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
-    const ScanPlan p = plan_scan(T, d, d + 1, 1, batch, dtype, opts ? opts->chunk_len : 0);
-    if (int s = check_workspace(ctx, ws, ws_bytes, p.tot_bytes + p.car_bytes)) return s;
+    const ScanPlan p = plan_scan(T, d, d + 1, 1, batch, dtype, opts ? opts->chunk_len : 0, false);
+    if (int s = check_workspace(ctx, ws, ws_bytes, p.total())) return s;
     if (int s = need_ctx(ctx)) return s;
     const size_t cb = 2 * comp_bytes(dtype);
 
@@ -461,6 +577,8 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
     }
     unsigned char *totals = static_cast<unsigned char *>(ws);
     unsigned char *carries = totals + p.tot_bytes;
+    unsigned char *gtot = carries + p.car_bytes;
+    unsigned char *gcar = gtot + p.gtot_bytes;
     { // phase 1: augmented chunk products [A* | b*]
         ChainLaunch l = base;
         l.m = d + 1;
@@ -476,31 +594,14 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
         if (int s = launch_chain(ctx, l)) return s;
     }
     { // phase 2: h at the chunk boundaries
-        ChainLaunch l;
-        std::memset(&l, 0, sizeof l);
-        l.dtype = dtype;
-        l.n = d;
-        l.d = d;
-        l.m = 1;
-        l.batch = batch;
-        l.left_fact = 1;
-        l.left = totals;
-        l.left_batch_stride = (long long)p.C * p.tot.stride;
-        l.left_step_stride = (long long)p.tot.stride;
-        l.left_fact_cols = p.tot.cols_padded;
-        l.steps = p.C - 1;
-        l.chunk_len = p.C - 1;
-        l.chunks_launched = 1;
-        l.init_mode = h0 ? 2 : 3;
-        l.init = h0;
-        l.init_stride = (long long)d * cb;
-        l.bias_mode = 2;
-        l.bias_col = 0;
-        l.out_fact_steps = carries;
-        l.fact_stride = (long long)p.car.stride;
-        l.fact_cols = p.car.cols_padded;
-        l.label = "affine_phase2_carry_chain";
-        if (int s = launch_chain(ctx, l)) return s;
+        CarryState cs;
+        cs.m = 1;
+        cs.init_mode = h0 ? 2 : 3;
+        cs.init = h0;
+        cs.init_stride = (long long)d * cb;
+        cs.bias = true;
+        cs.final_goom = nullptr;
+        if (int s = carry_phase(ctx, p, dtype, d, batch, totals, carries, gtot, gcar, cs, "affine_phase2_carries")) return s;
     }
     { // phase 3: matrix-vector walk of every chunk
         ChainLaunch l = base;
@@ -511,6 +612,8 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
         l.init_mode = 1;
         l.init = carries;
         l.init_stride = (long long)p.car.stride;
+        l.init_group = p.S;
+        l.init_ngroups = p.G;
         l.fact_stride = (long long)p.car.stride;
         l.fact_cols = p.car.cols_padded;
         l.out_goom = H;

@@ -231,6 +231,14 @@ def test_scan_sizes_and_ragged_tails(G, oracle, T, d, chunk):
     run_scan_case(G, oracle, T, d, chunk, name=f"T{T}d{d}")
 
 
+def test_scan_many_chunks_grouped_carries(G, oracle):
+    # more than 96 chunks: the carry phase is itself a grouped scan (group products, their
+    # prefixes, groups re-walked); ragged last chunk and ragged last group
+    run_scan_case(G, oracle, 1203, 16, 4, name="301 chunks d16")
+    run_scan_case(G, oracle, 700, 32, 5, m=7, batch=2, seed=7, name="140 chunks d32 init")
+    run_scan_case(G, oracle, 389, 64, 3, name="130 chunks d64")
+
+
 def test_scan_with_initial_state_and_batch(G, oracle):
     run_scan_case(G, oracle, 120, 32, 16, m=32, batch=3, seed=1, name="init square batch3")
     run_scan_case(G, oracle, 120, 64, 25, m=1, batch=2, seed=2, name="init vector")
@@ -265,7 +273,8 @@ def test_scan_beyond_float_range(G, oracle):
 
 # ------------------------------------------------------------------------------ affine
 
-@pytest.mark.parametrize("T,d,batch,chunk", [(64, 8, 2, 0), (300, 32, 3, 32), (100, 16, 1, 9), (1, 32, 2, 0), (257, 64, 1, 40)])
+@pytest.mark.parametrize("T,d,batch,chunk", [(64, 8, 2, 0), (300, 32, 3, 32), (100, 16, 1, 9), (1, 32, 2, 0), (257, 64, 1, 40),
+                                             (1000, 32, 2, 5)])
 def test_affine_scan_matches_oracle(G, oracle, T, d, batch, chunk):
     A, b = si.recurrence_inputs(si.BASE_SEED + 50, batch, T, d)
     Az, bz = oracle.to_goom(A), oracle.to_goom(b)
