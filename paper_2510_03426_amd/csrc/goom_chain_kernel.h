@@ -26,6 +26,7 @@ namespace goom_chain {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef double d4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 
 constexpr double kLog2e = 1.44269504088896340736;
 constexpr double kLn2 = 0.693147180559945309417;
@@ -67,6 +68,38 @@ template <> struct Comp<float> {
     __device__ static float abs_(float x) { return __builtin_fabsf(x); }
     __device__ static float ceil_(float x) { return __builtin_ceilf(x); }
     __device__ static float neg_inf() { return -__builtin_huge_valf(); }
+    // max without NaN canonicalisation: the median of (a, b, +inf)
+    __device__ static float max_(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, __builtin_huge_valf()); }
+    template <int CTRL> __device__ static float dpp(float v)
+    {
+        const int iv = __builtin_bit_cast(int, v);
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(iv, iv, CTRL, 0xF, 0xF, false));
+    }
+    // max over lane l and lane l ^ 16 / l ^ 32, by swapping 16- / 32-lane rows between two copies
+    __device__ static float xor16_max(float v)
+    {
+        const unsigned u = __builtin_bit_cast(unsigned, v);
+        const u2 r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+        return max_(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+    }
+    __device__ static float xor32_max(float v)
+    {
+        const unsigned u = __builtin_bit_cast(unsigned, v);
+        const u2 r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        return max_(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+    }
+    // max over aligned groups of LANES lanes, result in every lane: cross-lane moves on
+    // the vector ALU (quad permutes, half-row and row mirrors, row swaps), no LDS traffic
+    template <int LANES> __device__ static float group_allmax(float v)
+    {
+        v = max_(v, dpp<0xB1>(v));                   // quad_perm [1,0,3,2]
+        v = max_(v, dpp<0x4E>(v));                   // quad_perm [2,3,0,1]
+        if (LANES >= 8) v = max_(v, dpp<0x141>(v));  // row_half_mirror
+        if (LANES >= 16) v = max_(v, dpp<0x140>(v)); // row_mirror
+        if (LANES >= 32) v = xor16_max(v);
+        if (LANES >= 64) v = xor32_max(v);
+        return v;
+    }
     // accumulator register v of lane group g holds row 4 g + v of the 16 x 16 tile
     __device__ static int row_of(int g, int v) { return 4 * g + v; }
     // position of logical index j inside LDS rows / the row-shift array
@@ -120,6 +153,15 @@ template <> struct Comp<double> {
     __device__ static double abs_(double x) { return __builtin_fabs(x); }
     __device__ static double ceil_(double x) { return __builtin_ceil(x); }
     __device__ static double neg_inf() { return -__builtin_huge_val(); }
+    __device__ static double max_(double a, double b) { return a > b ? a : b; }
+    __device__ static double xor16_max(double v) { return max_(v, __shfl_xor(v, 16, 64)); }
+    __device__ static double xor32_max(double v) { return max_(v, __shfl_xor(v, 32, 64)); }
+    template <int LANES> __device__ static double group_allmax(double v)
+    {
+#pragma unroll
+        for (int s = 1; s < LANES; s <<= 1) v = max_(v, __shfl_xor(v, s, 64));
+        return v;
+    }
     // the double-precision instruction interleaves rows: register v of lane group g holds row 4 v + g
     __device__ static int row_of(int g, int v) { return 4 * v + g; }
     // ... so contraction index 16 kt + 4 v + g is stored at position 16 kt + 4 g + v, which
@@ -176,7 +218,10 @@ constexpr int waves_per_simd(int comp_bytes, int dp, int nw)
     return (comp_bytes == 4 && dp <= 64 && nw >= dp / 16) ? 2 : (comp_bytes == 4 && dp <= 64) ? 2 : 1;
 }
 
-template <typename R, int DP, int NW, int LEFT_FACT>
+// FAST: the factor fills the padded tile exactly (n = d = DP), the state has whole
+// 16-column slabs and there is no bias column, so every bounds test and the bias path
+// compile away and the step is straight-line code.
+template <typename R, int DP, int NW, int LEFT_FACT, bool FAST>
 __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void chain_kernel(ChainArgs a)
 {
     constexpr int KT = DP / 16;
@@ -200,12 +245,12 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // wave-uniform, kept in a scalar register
     const int g = lane >> 4;
     const int c = lane & 15;
     const int n_rows = a.n, d = a.d, m = a.m;
     const int col = wave * 16 + c;
-    const bool slab_active = wave < a.nslabs;
+    const bool slab_active = FAST || wave < a.nslabs; // FAST: every wave owns a slab
     const R kNegInf = Comp<R>::neg_inf();
 
     const long long chain = blockIdx.x;
@@ -231,8 +276,8 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
         for (int q = 0; q < QB; ++q) {
             const int p = tid + (q0 + q) * NT;
             const int row = p / LPR, cj = 2 * (p % LPR);
-            const bool v0 = (p < NITEMS) && row < n_rows && cj < d;
-            const bool v1 = v0 && (cj + 1 < d);
+            const bool v0 = FAST || ((p < NITEMS) && row < n_rows && cj < d);
+            const bool v1 = FAST || (v0 && (cj + 1 < d));
             if (LEFT_FACT) {
                 // factored left factor: mantissas [DP][left_fact_cols], leading columns on one exponent
                 const R *mp = reinterpret_cast<const R *>(src) + (size_t)row * a.left_fact_cols + cj;
@@ -241,7 +286,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                 it[q].im0 = it[q].im1 = (R)0;
             } else {
                 const R *gp = reinterpret_cast<const R *>(src) + ((size_t)row * d + cj) * 2;
-                if (v1 && vec_ok) {
+                if (FAST || (v1 && vec_ok)) {
                     if (sizeof(R) == 4) {
                         const f4 w = *reinterpret_cast<const f4 *>(gp);
                         it[q].re0 = w[0]; it[q].im0 = w[1]; it[q].re1 = w[2]; it[q].im1 = w[3];
@@ -271,24 +316,20 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
             R x0, x1, n;
             if (LEFT_FACT) {
                 const R a0 = Comp<R>::abs_(it[q].re0), a1 = Comp<R>::abs_(it[q].re1);
-                R r = a0 > a1 ? a0 : a1;
-#pragma unroll
-                for (int s = 1; s < LPR; s <<= 1) r = wave_xor_max<R>(r, s);
+                const R r = Comp<R>::template group_allmax<LPR>(Comp<R>::max_(a0, a1));
                 const int e = (r > (R)0 && r < -kNegInf) ? Comp<R>::frexp_exp(r) : 0;
                 x0 = Comp<R>::ldexp_(it[q].re0, -e);
                 x1 = Comp<R>::ldexp_(it[q].re1, -e);
                 n = (R)e + common;
             } else {
-                R r = it[q].re0 > it[q].re1 ? it[q].re0 : it[q].re1;
-#pragma unroll
-                for (int s = 1; s < LPR; s <<= 1) r = wave_xor_max<R>(r, s);
+                const R r = Comp<R>::template group_allmax<LPR>(Comp<R>::max_(it[q].re0, it[q].re1));
                 n = Comp<R>::row_shift(r);
                 x0 = Comp<R>::exp2_shifted(it[q].re0, n);
                 x1 = Comp<R>::exp2_shifted(it[q].re1, n);
                 if (Comp<R>::is_negative(it[q].im0)) x0 = -x0;
                 if (Comp<R>::is_negative(it[q].im1)) x1 = -x1;
             }
-            if (p < NITEMS) {
+            if (FAST || p < NITEMS) {
                 tile[row * LDA + Comp<R>::phys(cj)] = x0;
                 tile[row * LDA + Comp<R>::phys(cj + 1)] = x1;
                 if (cp == 0) nsh[Comp<R>::phys(row)] = n;
@@ -428,7 +469,35 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
         vec4 acc[KT];
 #pragma unroll
         for (int mt = 0; mt < KT; ++mt) acc[mt] = vec4{0, 0, 0, 0};
-        if (slab_active) {
+        if (FAST) {
+            // Straight-line step: the product of this step and the exponentiation of the
+            // next factor (already in registers) are independent, so they sit in one
+            // scheduling region and the matrix instructions are interleaved with the
+            // vector work.  Past the end of the chain the last factor is converted and
+            // loaded again (clamped index) instead of branching; nobody reads the result.
+            const long long tn = t + 1 < len ? t + 1 : len - 1;
+            const long long tl = t + 2 < len ? t + 2 : len - 1;
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt) {
+                vec4 av[KT];
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+                    av[mt] = *reinterpret_cast<const vec4 *>(&tile[(16 * mt + c) * LDA + 16 * kt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int mt = 0; mt < KT; ++mt) acc[mt] = Comp<R>::mfma(av[mt][v], st[kt][v], acc[mt]);
+            }
+            if (PREFETCH && NBUF == 2) {
+                convert_items(tn, 0, pre, cur ^ 1);
+                load_items(tl, 0, pre);
+#pragma unroll
+                for (int i = 0; i < KT * KT * 4; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); // one matrix instruction
+                    __builtin_amdgcn_sched_group_barrier(0x002, 5, 0); // a few vector instructions
+                }
+            }
+        } else if (slab_active) {
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt) {
                 vec4 av[KT];
@@ -451,7 +520,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
         //
         // bias column (linear recurrence with bias): b_i, given as a GOOM or as a column
         // of the factored left factor, is added to entry (i, bias_col) in the log2 domain.
-        const bool bias_lane = a.bias_mode != 0 && slab_active && col == a.bias_col;
+        const bool bias_lane = !FAST && a.bias_mode != 0 && slab_active && col == a.bias_col;
         auto bias_term = [&](int i, double &blog, bool &bneg) { // blog = log2|b_i| - ecol
             blog = kNegBig;
             bneg = false;
@@ -480,7 +549,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
             for (int v = 0; v < 4; ++v) {
                 const R x = acc[mt][v];
                 const R lg = (x != (R)0) ? (R)Comp<R>::frexp_exp(x) + nv[v] : kNegInf;
-                cm = lg > cm ? lg : cm;
+                cm = Comp<R>::max_(lg, cm);
             }
         }
         if (bias_lane) {
@@ -495,20 +564,55 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                     cm = lb > cm ? lb : cm;
                 }
         }
-        cm = wave_xor_max<R>(cm, 16);
-        cm = wave_xor_max<R>(cm, 32);
+        cm = Comp<R>::xor32_max(Comp<R>::xor16_max(cm));
         if (bias_lane) cm += (R)2; // room for the sum of two terms
         const bool col_nonzero = cm > kNegInf;
         const R cms = col_nonzero ? cm : (R)0;
 
-        const bool want_out = a.out_goom && slab_active && col < m && (!a.out_goom_last_only || t == len - 1);
+        const bool want_out = a.out_goom && slab_active && (FAST || col < m) && (!a.out_goom_last_only || t == len - 1);
+        // (in FAST kernels every term above is wave-uniform)
         R *outp = nullptr;
         if (want_out) {
             long long o_idx = a.out_goom_last_only ? chain_global : (item * a.steps + t0 + t);
             outp = reinterpret_cast<R *>(a.out_goom) + ((size_t)o_idx * n_rows * m) * 2;
         }
 
-        if (!bias_lane) {
+        // rescale: entry <- entry 2^(n_i - cm), exact; the state's exponent takes cm
+        auto rescale = [&](R x, R n_i) {
+            R sh = n_i - cms;
+            sh = sh > (R)-4000 ? sh : (R)-4000;
+            sh = sh < (R)4000 ? sh : (R)4000;
+            return Comp<R>::ldexp_(x, (int)sh);
+        };
+        if (FAST) {
+            if (want_out) { // wave-uniform: one branch around all of this step's stores
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt) {
+                    const vec4 nv = *reinterpret_cast<const vec4 *>(&nsh[16 * mt + 4 * g]);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int i = 16 * mt + Comp<R>::row_of(g, v);
+                        const R x = acc[mt][v];
+                        const R re = Comp<R>::out_re(x, nv[v], ecol);
+                        const R im = x < (R)0 ? Comp<R>::pi() : (R)0;
+                        R *o = outp + ((size_t)i * m + col) * 2;
+                        if (sizeof(R) == 4) {
+                            *reinterpret_cast<float2 *>(o) = float2{(float)re, (float)im};
+                        } else {
+                            *reinterpret_cast<double2 *>(o) = double2{(double)re, (double)im};
+                        }
+                        st[mt][v] = rescale(x, nv[v]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt) {
+                    const vec4 nv = *reinterpret_cast<const vec4 *>(&nsh[16 * mt + 4 * g]);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) st[mt][v] = rescale(acc[mt][v], nv[v]);
+                }
+            }
+        } else if (!bias_lane) {
 #pragma unroll
             for (int mt = 0; mt < KT; ++mt) {
                 const vec4 nv = *reinterpret_cast<const vec4 *>(&nsh[16 * mt + 4 * g]);
@@ -526,10 +630,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                             *reinterpret_cast<double2 *>(o) = double2{(double)re, (double)im};
                         }
                     }
-                    R sh = nv[v] - cms;
-                    sh = sh > (R)-4000 ? sh : (R)-4000;
-                    sh = sh < (R)4000 ? sh : (R)4000;
-                    st[mt][v] = Comp<R>::ldexp_(x, (int)sh);
+                    st[mt][v] = rescale(x, nv[v]);
                 }
             }
         } else {
@@ -544,10 +645,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                     bool bneg;
                     bias_term(i, blog, bneg);
                     // entry = x 2^(n_i - cm) + (+-) 2^(blog - cm), in units of 2^(ecol + cm)
-                    R sh = nv[v] - cms;
-                    sh = sh > (R)-4000 ? sh : (R)-4000;
-                    sh = sh < (R)4000 ? sh : (R)4000;
-                    const R xa = Comp<R>::ldexp_(x, (int)sh);
+                    const R xa = rescale(x, nv[v]);
                     const R xb = (col_nonzero && blog > kNegBig) ? exp2_of<R>(blog - (double)cm) : (R)0;
                     const R xs = xa + (bneg ? -xb : xb);
                     if (want_out && i < n_rows) {
@@ -565,7 +663,9 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
 
         // ------------------------------------------------------------ next left factor
         if (NBUF == 1) __syncthreads(); // every wave is done reading the only tile
-        if (t + 1 < len) {
+        if (FAST && PREFETCH && NBUF == 2) {
+            // the next factor was converted beside the product above
+        } else if (t + 1 < len) {
             const int nxt = NBUF == 2 ? (cur ^ 1) : 0;
             if (PREFETCH) {
                 convert_items(t + 1, 0, pre, nxt);
@@ -581,13 +681,13 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
     if (a.out_fact_final) store_fact(a.out_fact_final + chain_global * a.fact_stride, a.final_common_exponent != 0);
 }
 
-template <typename R, int DP, int NW, int LEFT_FACT> int launch_one(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
+template <typename R, int DP, int NW, int LEFT_FACT, bool FAST> int launch_one(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
 {
     constexpr int LDA = DP + Comp<R>::kPad;
     const size_t buf = (size_t)DP * LDA * sizeof(R) + (size_t)DP * sizeof(double);
     const int nbuf = (2 * buf + 64 <= 160 * 1024) ? 2 : 1;
     size_t lds = nbuf * buf + 64;
-    auto kern = chain_kernel<R, DP, NW, LEFT_FACT>;
+    auto kern = chain_kernel<R, DP, NW, LEFT_FACT, FAST>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return goom::check_hip(ctx, e, "hipFuncSetAttribute(chain_kernel)");
@@ -602,8 +702,11 @@ template <typename R, int DP, int NW, int LEFT_FACT> int launch_one(goom_ctx *ct
 
 template <typename R, int LEFT_FACT> int dispatch(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label)
 {
-#define GOOM_CASE(DPV, NWV) \
-    if (dp == DPV && nw == NWV) return launch_one<R, DPV, NWV, LEFT_FACT>(ctx, args, grid, label);
+    const bool fast = args.n == dp && args.d == dp && args.m == 16 * nw && args.bias_mode == 0;
+#define GOOM_CASE(DPV, NWV)                                                                           \
+    if (dp == DPV && nw == NWV)                                                                       \
+        return fast ? launch_one<R, DPV, NWV, LEFT_FACT, true>(ctx, args, grid, label)                \
+                    : launch_one<R, DPV, NWV, LEFT_FACT, false>(ctx, args, grid, label);
     GOOM_CASE(16, 1)
     GOOM_CASE(16, 2)
     GOOM_CASE(32, 1)
