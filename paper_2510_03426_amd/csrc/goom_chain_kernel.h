@@ -68,37 +68,43 @@ template <> struct Comp<float> {
     __device__ static float abs_(float x) { return __builtin_fabsf(x); }
     __device__ static float ceil_(float x) { return __builtin_ceilf(x); }
     __device__ static float neg_inf() { return -__builtin_huge_valf(); }
-    // max without NaN canonicalisation: the median of (a, b, +inf)
-    __device__ static float max_(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, __builtin_huge_valf()); }
-    template <int CTRL> __device__ static float dpp(float v)
+    __device__ static float max_(float a, float b) { return a > b ? a : b; }
+    // Cross-lane maxima run on integer keys (a monotone map of the float bits), so that
+    // each step is one integer max with a lane-permuted operand on the vector ALU: quad
+    // permutes, half-row and row mirrors, then 16- and 32-lane row swaps.  No LDS traffic.
+    __device__ static int key_of(float x)
     {
-        const int iv = __builtin_bit_cast(int, v);
-        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(iv, iv, CTRL, 0xF, 0xF, false));
+        const int b = __builtin_bit_cast(int, x);
+        return b ^ ((b >> 31) & 0x7fffffff);
     }
-    // max over lane l and lane l ^ 16 / l ^ 32, by swapping 16- / 32-lane rows between two copies
-    __device__ static float xor16_max(float v)
+    __device__ static float of_key(int k) { return __builtin_bit_cast(float, k ^ ((k >> 31) & 0x7fffffff)); }
+    __device__ static int imax(int a, int b) { return a > b ? a : b; }
+    template <int CTRL> __device__ static int dpp(int v) { return __builtin_amdgcn_mov_dpp(v, CTRL, 0xF, 0xF, true); }
+    __device__ static int xor16_imax(int v)
     {
-        const unsigned u = __builtin_bit_cast(unsigned, v);
-        const u2 r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-        return max_(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+        const u2 r = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+        return imax((int)r[0], (int)r[1]);
     }
-    __device__ static float xor32_max(float v)
+    __device__ static int xor32_imax(int v)
     {
-        const unsigned u = __builtin_bit_cast(unsigned, v);
-        const u2 r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-        return max_(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+        const u2 r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+        return imax((int)r[0], (int)r[1]);
     }
-    // max over aligned groups of LANES lanes, result in every lane: cross-lane moves on
-    // the vector ALU (quad permutes, half-row and row mirrors, row swaps), no LDS traffic
-    template <int LANES> __device__ static float group_allmax(float v)
+    // max over lane l and lane l ^ 16 / l ^ 32
+    __device__ static float xor16_max(float v) { return of_key(xor16_imax(key_of(v))); }
+    __device__ static float xor32_max(float v) { return of_key(xor32_imax(key_of(v))); }
+    __device__ static float xor16_32_max(float v) { return of_key(xor32_imax(xor16_imax(key_of(v)))); }
+    // max of a and b over aligned groups of LANES lanes, result in every lane
+    template <int LANES> __device__ static float group_allmax(float a, float b)
     {
-        v = max_(v, dpp<0xB1>(v));                   // quad_perm [1,0,3,2]
-        v = max_(v, dpp<0x4E>(v));                   // quad_perm [2,3,0,1]
-        if (LANES >= 8) v = max_(v, dpp<0x141>(v));  // row_half_mirror
-        if (LANES >= 16) v = max_(v, dpp<0x140>(v)); // row_mirror
-        if (LANES >= 32) v = xor16_max(v);
-        if (LANES >= 64) v = xor32_max(v);
-        return v;
+        int v = imax(key_of(a), key_of(b));
+        v = imax(v, dpp<0xB1>(v));                   // quad_perm [1,0,3,2]
+        v = imax(v, dpp<0x4E>(v));                   // quad_perm [2,3,0,1]
+        if (LANES >= 8) v = imax(v, dpp<0x141>(v));  // row_half_mirror
+        if (LANES >= 16) v = imax(v, dpp<0x140>(v)); // row_mirror
+        if (LANES >= 32) v = xor16_imax(v);
+        if (LANES >= 64) v = xor32_imax(v);
+        return of_key(v);
     }
     // accumulator register v of lane group g holds row 4 g + v of the 16 x 16 tile
     __device__ static int row_of(int g, int v) { return 4 * g + v; }
@@ -110,6 +116,21 @@ template <> struct Comp<float> {
         int k = (int)__builtin_rintf(im * 0.318309886183790671538f);
         return (k & 1) != 0;
     }
+    // x with its sign flipped when im is an odd multiple of pi: the parity bit of
+    // round(im / pi) is moved onto the sign bit
+    __device__ static float apply_sign(float x, float im)
+    {
+        const int k = (int)__builtin_rintf(im * 0.318309886183790671538f);
+        return __builtin_bit_cast(float, __builtin_bit_cast(int, x) ^ (k << 31));
+    }
+    // binary exponent of x in the frexp convention (|x| = m 2^e, 1/2 <= m < 1), as a float;
+    // zero counts as 2^-126 (it only has to lose every comparison that matters)
+    __device__ static float exponent_of(float x)
+    {
+        const unsigned b = __builtin_bit_cast(unsigned, x);
+        return (float)(int)((b >> 23) & 0xffu) - 126.0f;
+    }
+    __device__ static float clamp_shift(float sh) { return __builtin_amdgcn_fmed3f(sh, -4000.0f, 4000.0f); }
     // row shift for a row whose largest log-magnitude is r: a whole number near r log2(e)
     __device__ static float row_shift(float r) { return r > neg_inf() ? __builtin_ceilf(r * 1.44269504088896340736f) : 0.0f; }
     // 2^(re log2(e) - n) for a whole number n >= re log2(e) (about): the product with
@@ -120,14 +141,14 @@ template <> struct Comp<float> {
 #pragma clang fp contract(off) // p_hi must stay a rounded product: p_lo is its rounding error
         const float kHi = 1.44269502162933349609375f;  // float nearest log2(e)
         const float kLo = 1.925963033500011e-8f;       // log2(e) - kHi
-        float p_hi = re * kHi;
+        const float kLn2 = 0.693147182464599609375f;
+        const float p_hi = re * kHi;
         float p_lo = __builtin_fmaf(re, kHi, -p_hi);
         p_lo = __builtin_fmaf(re, kLo, p_lo);
-        float t_hi = p_hi - n;
-        float k = __builtin_rintf(t_hi);
-        float f = (t_hi - k) + p_lo;
-        float y = __builtin_ldexpf(__builtin_amdgcn_exp2f(f), (int)k);
-        return t_hi > -160.0f ? y : 0.0f; // false for -inf and NaN as well: they become zero
+        const float t_hi = p_hi - n;                    // exact where it matters (like magnitudes)
+        const float y = __builtin_amdgcn_exp2f(t_hi);   // hardware 2^x on an exactly represented argument
+        const float yc = __builtin_fmaf(y, p_lo * kLn2, y); // 2^(t_hi + p_lo) = 2^t_hi (1 + p_lo ln 2 + O(p_lo^2)), |p_lo| < 2^-17
+        return t_hi > -150.0f ? yc : 0.0f; // false for -inf and NaN as well: they become zero
     }
     // log-magnitude (natural log) of x 2^(n + e), rounded to the component type; x = 0 -> -inf
     __device__ static float out_re(float x, float n, double e)
@@ -156,8 +177,10 @@ template <> struct Comp<double> {
     __device__ static double max_(double a, double b) { return a > b ? a : b; }
     __device__ static double xor16_max(double v) { return max_(v, __shfl_xor(v, 16, 64)); }
     __device__ static double xor32_max(double v) { return max_(v, __shfl_xor(v, 32, 64)); }
-    template <int LANES> __device__ static double group_allmax(double v)
+    __device__ static double xor16_32_max(double v) { return xor32_max(xor16_max(v)); }
+    template <int LANES> __device__ static double group_allmax(double a, double b)
     {
+        double v = max_(a, b);
 #pragma unroll
         for (int s = 1; s < LANES; s <<= 1) v = max_(v, __shfl_xor(v, s, 64));
         return v;
@@ -172,6 +195,9 @@ template <> struct Comp<double> {
         long long k = (long long)__builtin_rint(im * 0.318309886183790671538);
         return (k & 1LL) != 0;
     }
+    __device__ static double apply_sign(double x, double im) { return is_negative(im) ? -x : x; }
+    __device__ static double exponent_of(double x) { return x != 0.0 ? (double)frexp_exp(x) : -1022.0; }
+    __device__ static double clamp_shift(double sh) { return sh > -4000.0 ? (sh < 4000.0 ? sh : 4000.0) : -4000.0; }
     __device__ static double row_shift(double r) { return r > neg_inf() ? __builtin_ceil(r * kLog2e) : 0.0; }
     __device__ static double exp2_shifted(double re, double n)
     {
@@ -312,27 +338,25 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
             const int p = tid + (q0 + q) * NT;
-            const int row = p / LPR, cp = p % LPR, cj = 2 * cp;
+            const int row = p / LPR, cj = 2 * (p % LPR);
             R x0, x1, n;
             if (LEFT_FACT) {
                 const R a0 = Comp<R>::abs_(it[q].re0), a1 = Comp<R>::abs_(it[q].re1);
-                const R r = Comp<R>::template group_allmax<LPR>(Comp<R>::max_(a0, a1));
+                const R r = Comp<R>::template group_allmax<LPR>(a0, a1);
                 const int e = (r > (R)0 && r < -kNegInf) ? Comp<R>::frexp_exp(r) : 0;
                 x0 = Comp<R>::ldexp_(it[q].re0, -e);
                 x1 = Comp<R>::ldexp_(it[q].re1, -e);
                 n = (R)e + common;
             } else {
-                const R r = Comp<R>::template group_allmax<LPR>(Comp<R>::max_(it[q].re0, it[q].re1));
+                const R r = Comp<R>::template group_allmax<LPR>(it[q].re0, it[q].re1);
                 n = Comp<R>::row_shift(r);
-                x0 = Comp<R>::exp2_shifted(it[q].re0, n);
-                x1 = Comp<R>::exp2_shifted(it[q].re1, n);
-                if (Comp<R>::is_negative(it[q].im0)) x0 = -x0;
-                if (Comp<R>::is_negative(it[q].im1)) x1 = -x1;
+                x0 = Comp<R>::apply_sign(Comp<R>::exp2_shifted(it[q].re0, n), it[q].im0);
+                x1 = Comp<R>::apply_sign(Comp<R>::exp2_shifted(it[q].re1, n), it[q].im1);
             }
             if (FAST || p < NITEMS) {
                 tile[row * LDA + Comp<R>::phys(cj)] = x0;
                 tile[row * LDA + Comp<R>::phys(cj + 1)] = x1;
-                if (cp == 0) nsh[Comp<R>::phys(row)] = n;
+                nsh[Comp<R>::phys(row)] = n; // every lane of the row writes the same value
             }
         }
     };
@@ -548,7 +572,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const R x = acc[mt][v];
-                const R lg = (x != (R)0) ? (R)Comp<R>::frexp_exp(x) + nv[v] : kNegInf;
+                const R lg = Comp<R>::exponent_of(x) + nv[v];
                 cm = Comp<R>::max_(lg, cm);
             }
         }
@@ -564,7 +588,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                     cm = lb > cm ? lb : cm;
                 }
         }
-        cm = Comp<R>::xor32_max(Comp<R>::xor16_max(cm));
+        cm = Comp<R>::xor16_32_max(cm);
         if (bias_lane) cm += (R)2; // room for the sum of two terms
         const bool col_nonzero = cm > kNegInf;
         const R cms = col_nonzero ? cm : (R)0;
@@ -579,10 +603,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
 
         // rescale: entry <- entry 2^(n_i - cm), exact; the state's exponent takes cm
         auto rescale = [&](R x, R n_i) {
-            R sh = n_i - cms;
-            sh = sh > (R)-4000 ? sh : (R)-4000;
-            sh = sh < (R)4000 ? sh : (R)4000;
-            return Comp<R>::ldexp_(x, (int)sh);
+            return Comp<R>::ldexp_(x, (int)Comp<R>::clamp_shift(n_i - cms));
         };
         if (FAST) {
             if (want_out) { // wave-uniform: one branch around all of this step's stores
