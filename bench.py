@@ -86,7 +86,10 @@ def main():
     nprof = max(1, min(args.steps, 5))
     for _ in range(nprof):
         step()
-        for label, ms in g.profile_records():
+        per_call = {}
+        for label, ms in g.profile_records():  # a phase may be several launches: add them up
+            per_call[label] = per_call.get(label, 0.0) + ms
+        for label, ms in per_call.items():
             kern.setdefault(label, []).append(ms)
     g.profile_enable(False)
     kern_avg = {k: sum(v) / len(v) for k, v in kern.items()}
@@ -139,6 +142,16 @@ def main():
         result["reduce"] = {"ms": round(rms, 4), "products_per_s": round(T / (rms * 1e-3), 1),
                             "hbm_gbs": round(T * 8 * d * d / (rms * 1e-3) / 1e9, 1)}
         result["to_goom_gbs"] = round(z.numel() * 12 / t_codec / 1e9, 1)
+        # what this machine's HBM sustains for a plain device-to-device copy of the same size
+        # (read + write bytes over time): the practical ceiling beside the published 8 TB/s
+        out.copy_(z)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for _ in range(3):
+            out.copy_(z)
+        torch.cuda.synchronize()
+        cms = (time.perf_counter() - c0) / 3
+        result["hbm_copy_gbs"] = round(2 * z.numel() * 8 / cms / 1e9, 1)
 
     # ---- CPU oracle on a bounded sample of the same workload (reported, not a target)
     if args.cpu_sample_steps > 0:

@@ -1,9 +1,10 @@
 // chain kernel instantiations: float components, left factors as GOOMs
-#include "goom_chain_kernel.h"
+#include "goom_chain_fast.h"
 
 namespace goom_chain {
 int dispatch_f32_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label)
 {
+    if (fast_applies(args, dp, nw)) return dispatch_fast(ctx, args, dp, grid, label);
     return dispatch<float, 0>(ctx, args, dp, nw, grid, label);
 }
 } // namespace goom_chain

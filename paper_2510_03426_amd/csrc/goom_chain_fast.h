@@ -1,0 +1,340 @@
+// Hot variant of the chain kernel: float components, left factors given as GOOMs that
+// fill the padded tile exactly (d = 16, 32, 64 or 128), state of 16 * NW columns, no bias.
+// This is the kernel the long scans spend their time in (phase 1 and phase 3 of the
+// three-phase scan; paper Section 4.1), and LMME on such shapes (Section 3.2).
+//
+// On this chip the float matrix instructions run at the rate of the vector ALU and do
+// not overlap with it, so a step costs (matrix cycles) + 4 x (vector instructions) and
+// the design goal is to spend as few vector instructions per element as possible:
+//   * a lane loads four adjacent elements (two 16-byte loads), so a row's maximum needs
+//     three local and log2(lanes per row) cross-lane integer maxima on the vector ALU;
+//   * exponentiation is two fused multiply-adds and one hardware exp2 per element; the
+//     sign is the parity bit of round(im / pi) moved onto the sign bit;
+//   * the running product is NOT rescaled after a step.  The row exponents n_i that the
+//     step leaves behind are folded into the exponent arguments of the next factor's
+//     columns instead (the next product contracts over exactly those rows), which costs
+//     one subtraction per element there and nothing here.  Columns are renormalised by a
+//     power of two every few steps only, to stay inside float range;
+//   * output addresses are lane base + compile-time offsets.
+#pragma once
+#include "goom_chain_kernel.h"
+
+namespace goom_chain {
+
+struct Item4 {
+    f4 a, b; // (re0, im0, re1, im1), (re2, im2, re3, im3)
+};
+
+__device__ inline float vmax_raw(float x, float y)
+{
+    // plain v_max_f32: the compiler's own max first canonicalises both operands
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+}
+
+template <int DP, int NW>
+__global__ __launch_bounds__(NW * 64, (DP <= 64 ? 2 : 1)) void chain_kernel_fast(ChainArgs a)
+{
+    typedef Comp<float> C;
+    constexpr int KT = DP / 16;
+    constexpr int LDA = DP + 4;
+    constexpr int M = 16 * NW;   // state columns
+    constexpr int NT = NW * 64;
+    constexpr int LPR = DP / 4;  // lanes per row of the factor
+    constexpr int NITEMS = DP * LPR;
+    constexpr int Q = NITEMS / NT; // items per thread
+    constexpr int kRenormEvery = 4;
+    static_assert(NITEMS % NT == 0 && NT % LPR == 0, "tile does not divide among the threads");
+    constexpr size_t kTileBytes = (size_t)DP * LDA * sizeof(float);
+    constexpr size_t kBufBytes = kTileBytes + (size_t)DP * sizeof(float);
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    auto tile_of = [&](int b) { return reinterpret_cast<float *>(smem + (size_t)b * kBufBytes); };
+    auto nsh_of = [&](int b) { return reinterpret_cast<float *>(smem + (size_t)b * kBufBytes + kTileBytes); };
+    double *wave_red = reinterpret_cast<double *>(smem + 2 * kBufBytes);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4;
+    const int c = lane & 15;
+    const int col = wave * 16 + c;
+    const int c4 = 4 * (tid % LPR); // first of this lane's four factor columns
+
+    const long long chain = blockIdx.x;
+    const long long item = chain / a.chunks_launched;
+    const long long chunk = chain % a.chunks_launched;
+    const long long t0 = chunk * a.chunk_len;
+    long long len = a.steps - t0;
+    if (len > a.chunk_len) len = a.chunk_len;
+    const long long chain_global = item * a.chunks_per_item + chunk;
+    const unsigned char *left0 = a.left + item * a.left_batch_stride + t0 * a.left_step_stride;
+
+    auto load_items = [&](long long t, Item4 (&it)[Q]) {
+        const float *src = reinterpret_cast<const float *>(left0 + t * a.left_step_stride);
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const int row = (tid + q * NT) / LPR;
+            const f4 *gp = reinterpret_cast<const f4 *>(src + ((size_t)row * DP + c4) * 2);
+            it[q].a = gp[0];
+            it[q].b = gp[1];
+        }
+    };
+
+    // tile[i][j] = (+-) 2^(log2|A_ij| + r_j - n_i),  n_i = ceil(max_j (log2|A_ij| + r_j)),
+    // r_j = row exponents still attached to the running product (zero at the start).
+    auto convert_items = [&](const Item4 (&it)[Q], int buf, const float *rsrc) {
+        const float kHi = 1.44269502162933349609375f; // float nearest log2(e)
+        const float kLo = 1.925963033500011e-8f;      // log2(e) - kHi
+        float *tile = tile_of(buf);
+        float *nsh = nsh_of(buf);
+        f4 rj = {0.f, 0.f, 0.f, 0.f};
+        if (rsrc) rj = *reinterpret_cast<const f4 *>(&rsrc[c4]);
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const int row = (tid + q * NT) / LPR;
+            const float re[4] = {it[q].a[0], it[q].a[2], it[q].b[0], it[q].b[2]};
+            const float im[4] = {it[q].a[1], it[q].a[3], it[q].b[1], it[q].b[3]};
+            // row maximum of log2|A_ij| + r_j, to within rounding (any nearby whole number serves)
+            float u = __builtin_fmaf(re[0], kHi, rj[0]);
+#pragma unroll
+            for (int e = 1; e < 4; ++e) u = vmax_raw(u, __builtin_fmaf(re[e], kHi, rj[e]));
+            int key = C::key_of(u);
+            key = C::imax(key, C::dpp<0xB1>(key));
+            if (LPR >= 4) key = C::imax(key, C::dpp<0x4E>(key));
+            if (LPR >= 8) key = C::imax(key, C::dpp<0x141>(key));
+            if (LPR >= 16) key = C::imax(key, C::dpp<0x140>(key));
+            if (LPR >= 32) key = C::xor16_imax(key);
+            float mx = C::of_key(key);
+            // a row that is entirely zero keeps a finite (hugely negative) shift, and its
+            // exponent arguments are forced to -inf so that nothing can overflow
+            const bool zero_row = !(mx > -1.0e30f);
+            const float n = zero_row ? -1.0e30f : __builtin_ceilf(mx);
+            const float nsub = zero_row ? __builtin_huge_valf() : n;
+            f4 y;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                // exponent argument with one rounding at its own (small) magnitude, then the low part of log2(e)
+                float t = __builtin_fmaf(re[e], kHi, rj[e] - nsub);
+                t = __builtin_fmaf(re[e], kLo, t);
+                const float v = __builtin_amdgcn_exp2f(t); // 2^-inf = 0 covers zero entries
+                // parity of round(im / pi), read off the last mantissa bit after adding 1.5 * 2^23
+                const float kf = __builtin_fmaf(im[e], 0.318309886183790671538f, 12582912.0f);
+                y[e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) ^ (__builtin_bit_cast(int, kf) << 31));
+            }
+            *reinterpret_cast<f4 *>(&tile[row * LDA + c4]) = y;
+            nsh[row] = n; // every lane of the row writes the same value
+        }
+    };
+
+    // ------------------------------------------------------------------ initial state
+    float st[KT][4]; // st[kt][v] = W[16 kt + 4 g + v][col]
+    double ecol = 0.0;
+    const size_t fact_mant_bytes = (size_t)DP * a.fact_cols * sizeof(float);
+    if (a.init_mode == 0 || a.init_mode == 3) {
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) st[kt][v] = (a.init_mode == 0 && 16 * kt + 4 * g + v == col) ? 1.0f : 0.0f;
+    } else if (a.init_mode == 1) {
+        long long iidx = chain_global;
+        if (a.init_group > 0) {
+            long long grp = chunk / a.init_group;
+            if (grp >= a.init_ngroups) grp = a.init_ngroups - 1;
+            iidx = (item * a.init_ngroups + grp) * (a.init_group + 1) + (chunk - grp * a.init_group);
+        }
+        const unsigned char *ip = a.init + iidx * a.init_stride;
+        const float *mp = reinterpret_cast<const float *>(ip);
+        const double *ep = reinterpret_cast<const double *>(ip + fact_mant_bytes);
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) st[kt][v] = mp[(size_t)(16 * kt + 4 * g + v) * a.fact_cols + col];
+        ecol = ep[col];
+    } else {
+        const float *gp = reinterpret_cast<const float *>(a.init + item * a.init_stride);
+        float cmax = C::neg_inf();
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) cmax = C::max_(cmax, gp[((size_t)(16 * kt + 4 * g + v) * M + col) * 2]);
+        cmax = C::xor16_32_max(cmax);
+        ecol = (cmax > C::neg_inf()) ? __builtin_ceil((double)cmax * kLog2e) : 0.0;
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float *e = gp + ((size_t)(16 * kt + 4 * g + v) * M + col) * 2;
+                const float x = exp2_of<float>(__builtin_fma((double)e[0], kLog2e, -ecol));
+                st[kt][v] = C::apply_sign(x, e[1]);
+            }
+    }
+
+    Item4 pre[Q];
+    if (len > 0) {
+        load_items(0, pre);
+        convert_items(pre, 0, nullptr);
+        load_items(len > 1 ? 1 : 0, pre);
+    }
+    __syncthreads();
+
+    for (long long t = 0; t < len; ++t) {
+        const int cur = (int)(t & 1);
+        const float *tile = tile_of(cur);
+        const float *nsh = nsh_of(cur);
+        const bool last = t == len - 1;
+
+        // ------------------------------------------------------------ product, and next factor beside it
+        f4 acc[KT];
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) acc[mt] = f4{0, 0, 0, 0};
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            f4 av[KT];
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt)
+                av[mt] = *reinterpret_cast<const f4 *>(&tile[(16 * mt + c) * LDA + 16 * kt + 4 * g]);
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt) acc[mt] = C::mfma(av[mt][v], st[kt][v], acc[mt]);
+        }
+        // Past the end of the chain the last factor is converted and loaded once more
+        // (clamped index) rather than branching; nobody reads the result.
+        convert_items(pre, cur ^ 1, nsh);
+        load_items(t + 2 < len ? t + 2 : len - 1, pre);
+
+        // ------------------------------------------------------------ outputs
+        // entry (i = 16 mt + 4 g + v, col) of the product is acc 2^(n_i + ecol)
+        const bool want_out = a.out_goom && (!a.out_goom_last_only || last);
+        if (want_out) {
+            const long long o_idx = a.out_goom_last_only ? chain_global : (item * a.steps + t0 + t);
+            float *outp = reinterpret_cast<float *>(a.out_goom) + ((size_t)o_idx * DP * M + (size_t)(4 * g) * M + col) * 2;
+            const float ecol_f = (float)ecol;
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                const f4 nv = *reinterpret_cast<const f4 *>(&nsh[16 * mt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float x = acc[mt][v];
+                    const float re = C::out_re_f(x, nv[v] + ecol_f);
+                    const float im = x < 0.0f ? C::pi() : 0.0f;
+                    *reinterpret_cast<float2 *>(outp + (size_t)(16 * mt + v) * M * 2) = float2{re, im};
+                }
+            }
+        }
+
+        // ------------------------------------------------------------ state for the next step
+        if (!last) {
+            // keep the raw product; its row exponents n_i go to the next factor's columns
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) st[mt][v] = acc[mt][v];
+            if ((t % kRenormEvery) == kRenormEvery - 1) {
+                float cm = -300.0f;
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) cm = C::max_(cm, C::exponent_of(st[mt][v]));
+                cm = C::xor16_32_max(cm);
+                const int sh = -(int)cm;
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) st[mt][v] = __builtin_ldexpf(st[mt][v], sh);
+                ecol += (double)cm;
+            }
+        } else {
+            // last step: fold the row exponents into the mantissas, one exponent per column
+            float cm = C::neg_inf();
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                const f4 nv = *reinterpret_cast<const f4 *>(&nsh[16 * mt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) cm = C::max_(cm, C::exponent_of(acc[mt][v]) + nv[v]);
+            }
+            cm = C::xor16_32_max(cm);
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                const f4 nv = *reinterpret_cast<const f4 *>(&nsh[16 * mt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    st[mt][v] = __builtin_ldexpf(acc[mt][v], (int)C::clamp_shift(nv[v] - cm));
+            }
+            ecol += (double)cm;
+        }
+        __syncthreads();
+    }
+
+    if (a.out_fact_final) {
+        // factored product of the chain, all columns on one exponent (it becomes a left factor)
+        unsigned char *dst = a.out_fact_final + chain_global * a.fact_stride;
+        float *mp = reinterpret_cast<float *>(dst);
+        double *ep = reinterpret_cast<double *>(dst + fact_mant_bytes);
+        float cm = 0.0f;
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) cm = C::max_(cm, __builtin_fabsf(st[kt][v]));
+        cm = C::xor16_32_max(cm);
+        double ev = cm > 0.0f ? ecol : kNegBig;
+#pragma unroll
+        for (int s = 1; s < 16; s <<= 1) {
+            const double o = shfl_xor_double(ev, s);
+            ev = o > ev ? o : ev;
+        }
+        if (lane == 0) wave_red[wave] = ev;
+        __syncthreads();
+        double emax = kNegBig;
+        for (int w = 0; w < NW; ++w) emax = wave_red[w] > emax ? wave_red[w] : emax;
+        if (emax == kNegBig) emax = 0.0;
+        double dsh = ecol - emax;
+        dsh = dsh > -4000.0 ? dsh : -4000.0;
+        const int shift = cm > 0.0f ? (int)dsh : 0;
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                mp[(size_t)(16 * kt + 4 * g + v) * a.fact_cols + col] = __builtin_ldexpf(st[kt][v], shift);
+        if (g == 0) ep[col] = emax;
+    }
+}
+
+template <int DP, int NW> int launch_fast(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
+{
+    constexpr int LDA = DP + 4;
+    const size_t lds = 2 * ((size_t)DP * LDA * sizeof(float) + (size_t)DP * sizeof(float)) + 64;
+    auto kern = chain_kernel_fast<DP, NW>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return goom::check_hip(ctx, e, "hipFuncSetAttribute(chain_kernel_fast)");
+    }
+    if (grid <= 0) return GOOM_OK;
+    if (grid > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many chains for one launch (%lld)", grid);
+    goom::prof_begin(ctx, label);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds, ctx->stream, args);
+    goom::prof_end(ctx);
+    return goom::check_hip(ctx, hipGetLastError(), "launch chain_kernel_fast");
+}
+
+// The hot variant applies when the factor fills its padded tile, every wave owns a full
+// slab, there is no bias, and no per-step factored output is wanted.
+inline bool fast_applies(const ChainArgs &args, int dp, int nw)
+{
+    return args.n == dp && args.d == dp && args.m == 16 * nw && args.bias_mode == 0 && args.out_fact_steps == nullptr &&
+           ((dp == 16 && nw == 1) || (dp == 32 && nw == 2) || (dp == 64 && nw == 4) || (dp == 128 && nw == 8));
+}
+
+inline int dispatch_fast(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label)
+{
+    switch (dp) {
+    case 16: return launch_fast<16, 1>(ctx, args, grid, label);
+    case 32: return launch_fast<32, 2>(ctx, args, grid, label);
+    case 64: return launch_fast<64, 4>(ctx, args, grid, label);
+    default: return launch_fast<128, 8>(ctx, args, grid, label);
+    }
+}
+
+} // namespace goom_chain

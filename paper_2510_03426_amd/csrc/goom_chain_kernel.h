@@ -151,6 +151,15 @@ template <> struct Comp<float> {
         return t_hi > -150.0f ? yc : 0.0f; // false for -inf and NaN as well: they become zero
     }
     // log-magnitude (natural log) of x 2^(n + e), rounded to the component type; x = 0 -> -inf
+    // same with the exponents already summed: log-magnitude of x 2^s
+    __device__ static float out_re_f(float x, float s)
+    {
+#pragma clang fp contract(off)
+        const float kLn2Hi = 0.693147182464599609375f;
+        const float kLn2Lo = -1.90465429995776806e-9f;
+        const float l2 = __builtin_amdgcn_logf(__builtin_fabsf(x) * 4294967296.0f) - 32.0f;
+        return __builtin_fmaf(s, kLn2Hi, __builtin_fmaf(s, kLn2Lo, l2 * kLn2Hi));
+    }
     __device__ static float out_re(float x, float n, double e)
     {
 #pragma clang fp contract(off)
@@ -515,11 +524,6 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
             if (PREFETCH && NBUF == 2) {
                 convert_items(tn, 0, pre, cur ^ 1);
                 load_items(tl, 0, pre);
-#pragma unroll
-                for (int i = 0; i < KT * KT * 4; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); // one matrix instruction
-                    __builtin_amdgcn_sched_group_barrier(0x002, 5, 0); // a few vector instructions
-                }
             }
         } else if (slab_active) {
 #pragma unroll
