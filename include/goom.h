@@ -166,7 +166,9 @@ size_t goom_reduce_workspace_bytes(int64_t T, int d, int m, int64_t batch, int d
 
 typedef struct goom_reset_opts {
     int64_t chunk_len;    /* states are examined every chunk_len steps (t = chunk_len,
-                             2 chunk_len, ...); 0 = library default (64) */
+                             2 chunk_len, ...); 0 = library default (32).  Longer
+                             chunks shorten the serial phase; in float arithmetic they also blur
+                             the split between nearly equal exponents */
     int32_t policy;       /* GOOM_RESET_* */
     float cos_threshold;  /* used by GOOM_RESET_COLINEAR */
 } goom_reset_opts;

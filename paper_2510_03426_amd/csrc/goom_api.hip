@@ -355,6 +355,116 @@ static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, lon
     }
 }
 
+// ---- selectively reset scan ------------------------------------------------------------
+struct ResetPlan {
+    long long L, C;
+    int dp;
+    FactLayout tot, car;
+    size_t tot_bytes, car_bytes, flag_bytes;
+    size_t total() const { return tot_bytes + car_bytes + flag_bytes; }
+};
+
+static ResetPlan plan_reset(long long T, int d, long long batch, int dtype, const goom_reset_opts *opts)
+{
+    ResetPlan p;
+    p.L = (opts && opts->chunk_len > 0) ? opts->chunk_len : 32;
+    if (p.L > T) p.L = T;
+    p.C = (T + p.L - 1) / p.L;
+    p.dp = padded_dim(d);
+    p.tot = fact_layout(p.dp, d, dtype);
+    p.car = fact_layout(p.dp, d, dtype);
+    p.tot_bytes = (size_t)batch * p.C * p.tot.stride;
+    p.car_bytes = (size_t)batch * (p.C + 1) * p.car.stride;
+    p.flag_bytes = align_up((size_t)batch * p.C, 256);
+    return p;
+}
+
+static int run_reset(goom_ctx *ctx, const void *J, const void *S0, void *states, uint8_t *flags, double *growth,
+                     double growth_scale, long long T, int d, long long batch, int dtype, const goom_reset_opts *opts,
+                     void *ws, size_t ws_bytes)
+{
+    if (int s = check_common(ctx, dtype)) return s;
+    if (!J) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    if (T <= 0 || batch <= 0 || d <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive (T=%lld d=%d batch=%lld)", T, d, batch);
+    if (dtype != GOOM_C64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan is built for GOOM_C64 only");
+    if (d > 64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 64 (d=%d)", d);
+    if (opts && opts->chunk_len < 0) return fail(ctx, GOOM_EINVAL, "negative chunk_len");
+    const int policy = opts ? opts->policy : GOOM_RESET_ALWAYS;
+    if (policy < GOOM_RESET_NEVER || policy > GOOM_RESET_ALWAYS) return fail(ctx, GOOM_EINVAL, "unknown reset policy %d", policy);
+    if (!aligned(J, 16) || (S0 && !aligned(S0, 16)) || (states && !aligned(states, 16)))
+        return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
+    if (growth && !aligned(growth, 8)) return fail(ctx, GOOM_EINVAL, "growth must be 8-byte aligned");
+    const ResetPlan p = plan_reset(T, d, batch, dtype, opts);
+    if (int s = check_workspace(ctx, ws, ws_bytes, p.total())) return s;
+    if (int s = need_ctx(ctx)) return s;
+    const size_t cb = 2 * comp_bytes(dtype);
+    unsigned char *totals = static_cast<unsigned char *>(ws);
+    unsigned char *carries = totals + p.tot_bytes;
+    unsigned char *chunk_flags = carries + p.car_bytes;
+
+    ChainLaunch base;
+    std::memset(&base, 0, sizeof base);
+    base.dtype = dtype;
+    base.n = d;
+    base.d = d;
+    base.m = d;
+    base.batch = batch;
+    base.left = J;
+    base.left_batch_stride = (long long)T * d * d * cb;
+    base.left_step_stride = (long long)d * d * cb;
+    base.steps = T;
+    base.chunk_len = p.L;
+    base.chunks_launched = p.C;
+    { // phase 1: product of every chunk
+        ChainLaunch l = base;
+        l.init_mode = 0;
+        l.out_fact_final = totals;
+        l.final_common_exponent = 1;
+        l.fact_stride = (long long)p.tot.stride;
+        l.fact_cols = p.tot.cols_padded;
+        l.label = "reset_phase1_chunk_products";
+        if (int s = launch_chain(ctx, l)) return s;
+    }
+    ResetLaunch r;
+    std::memset(&r, 0, sizeof r);
+    r.totals = totals;
+    r.tot_stride = (long long)p.tot.stride;
+    r.tot_cols = p.tot.cols_padded;
+    r.carries = carries;
+    r.car_stride = (long long)p.car.stride;
+    r.car_cols = p.car.cols_padded;
+    r.s0 = S0;
+    r.post_states = states;
+    r.chunk_flags = chunk_flags;
+    r.flags = flags;
+    r.growth = growth;
+    r.growth_scale = growth_scale;
+    r.T = T;
+    r.L = p.L;
+    r.C = p.C;
+    r.batch = batch;
+    r.d = d;
+    r.policy = policy;
+    r.cos_threshold = opts ? opts->cos_threshold : 0.99f;
+    // phase 2: prefixes at the chunk boundaries, examined and reset in order
+    if (int s = launch_reset_carry(ctx, r)) return s;
+    if (states) { // phase 3: every chunk again from its incoming prefix, all states stored
+        ChainLaunch l = base;
+        l.init_mode = 1;
+        l.init = carries;
+        l.init_stride = (long long)p.car.stride;
+        l.init_group = p.C; // carries hold C + 1 entries per batch item
+        l.init_ngroups = 1;
+        l.fact_stride = (long long)p.car.stride;
+        l.fact_cols = p.car.cols_padded;
+        l.out_goom = states;
+        l.label = "reset_phase3_states";
+        if (int s = launch_chain(ctx, l)) return s;
+    }
+    if (states || flags) return launch_reset_post(ctx, r);
+    return GOOM_OK;
+}
+
 } // namespace goom
 
 using namespace goom;
@@ -624,28 +734,26 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
 
 size_t goom_scan_reset_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts)
 {
-    (void)T; (void)d; (void)batch; (void)dtype; (void)opts;
-    return 0;
+    if (T <= 0 || d <= 0 || batch <= 0 || d > 64 || dtype != GOOM_C64) return 0;
+    const ResetPlan p = plan_reset(T, d, batch, dtype, opts);
+    return p.total();
 }
 
 int goom_scan_reset(goom_ctx *ctx, const void *J, const void *S0, void *states, uint8_t *reset_flags, double *growth,
                     int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts, void *workspace,
                     size_t workspace_bytes)
 {
-    (void)J; (void)S0; (void)states; (void)reset_flags; (void)growth; (void)T; (void)d; (void)batch; (void)opts;
-    (void)workspace; (void)workspace_bytes;
-    if (int s = check_common(ctx, dtype)) return s;
-    return fail(ctx, GOOM_EUNSUPPORTED, "goom_scan_reset is not built yet");
+    return run_reset(ctx, J, S0, states, reset_flags, growth, 1.0, T, d, batch, dtype, opts, workspace, workspace_bytes);
 }
 
 int goom_lyapunov_spectrum(goom_ctx *ctx, const void *J, const void *S0, void *states, double *lambda, int64_t T, int d,
                            double dt, int64_t batch, int dtype, const goom_reset_opts *opts, void *workspace,
                            size_t workspace_bytes)
 {
-    (void)J; (void)S0; (void)states; (void)lambda; (void)T; (void)d; (void)dt; (void)batch; (void)opts;
-    (void)workspace; (void)workspace_bytes;
-    if (int s = check_common(ctx, dtype)) return s;
-    return fail(ctx, GOOM_EUNSUPPORTED, "goom_lyapunov_spectrum is not built yet");
+    if (!lambda) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    if (!(dt > 0.0)) return fail(ctx, GOOM_EINVAL, "dt must be positive");
+    return run_reset(ctx, J, S0, states, nullptr, lambda, 1.0 / (dt * (double)T), T, d, batch, dtype, opts, workspace,
+                     workspace_bytes);
 }
 
 } // extern "C"

@@ -87,6 +87,27 @@ struct ChainLaunch {
 };
 int launch_chain(goom_ctx *ctx, const ChainLaunch &a);
 
+struct ResetLaunch {
+    const void *totals;   // factored chunk products [batch][C]
+    long long tot_stride;
+    int tot_cols;
+    void *carries;        // factored prefixes [batch][C + 1]
+    long long car_stride;
+    int car_cols;
+    const void *s0;       // NULL or GOOM initial state [batch][d][d]
+    void *post_states;    // NULL or GOOM states [batch][T][d][d]
+    unsigned char *chunk_flags; // [batch][C] (workspace)
+    unsigned char *flags; // NULL or [batch][T]
+    double *growth;       // NULL or [batch][d]
+    double growth_scale;
+    long long T, L, C, batch;
+    int d;
+    int policy;
+    float cos_threshold;
+};
+int launch_reset_carry(goom_ctx *ctx, const ResetLaunch &l);
+int launch_reset_post(goom_ctx *ctx, const ResetLaunch &l);
+
 int launch_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, uint32_t flags);
 int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype);
 
