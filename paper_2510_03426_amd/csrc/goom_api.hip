@@ -587,7 +587,6 @@ int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batc
     if (batch <= 0 || n <= 0 || d <= 0 || m <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive");
     if (n > GOOM_MAX_DIM || d > GOOM_MAX_DIM || m > GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "n, d, m must be <= %d", GOOM_MAX_DIM);
     if (!aligned(A, 16) || !aligned(B, 16) || !aligned(C, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
-    if (flags & GOOM_LMME_EXACT) return fail(ctx, GOOM_EUNSUPPORTED, "GOOM_LMME_EXACT is not built yet");
     if (int s = need_ctx(ctx)) return s;
     const size_t cb = 2 * (dtype == GOOM_C64 ? 4 : 8);
     ChainLaunch l;
@@ -608,7 +607,9 @@ int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batc
     l.init_stride = (long long)d * m * cb;
     l.out_goom = C;
     l.label = "lmme";
-    return launch_chain(ctx, l);
+    if (int s = launch_chain(ctx, l)) return s;
+    if (flags & GOOM_LMME_EXACT) return launch_lmme_exact(ctx, A, B, C, batch, n, d, m, dtype);
+    return GOOM_OK;
 }
 
 size_t goom_scan_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype, const goom_scan_opts *opts)

@@ -108,6 +108,8 @@ struct ResetLaunch {
 int launch_reset_carry(goom_ctx *ctx, const ResetLaunch &l);
 int launch_reset_post(goom_ctx *ctx, const ResetLaunch &l);
 
+int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int n, int d, int m, int dtype);
+
 int launch_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, uint32_t flags);
 int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype);
 

@@ -199,6 +199,29 @@ def test_lmme_double_components(G, oracle):
     compare(got, re, sg, kap, name="lmme c128")
 
 
+@pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
+def test_lmme_wide_range_needs_exact_repair(G, oracle, ctype):
+    # log-magnitudes N(0, 200^2): after the row / column shifts nearly every term is below float
+    # range, so the scaled product alone returns zeros; the repair pass recomputes those outputs
+    from paper_2510_03426_amd import LMME_EXACT, LMME_FAST
+    b, n, d, m = 3, 128, 128, 128
+    A, B = si.wide_range_goom_pairs(si.BASE_SEED + 26, b, n, d, m, sigma=200.0, dtype=ctype)
+    say(f"lmme exact {np.dtype(ctype).name}: batch={b} {n}x{d}x{m}")
+    re, sg, kap = oracle.lmme(A, B, return_kappa=True)
+    fast = host(G.lmme(dev(A), dev(B), flags=LMME_FAST))
+    lost = np.isneginf(fast.real) & np.isfinite(re)
+    say(f"  scaled product alone: {lost.mean():.1%} of the outputs underflow to zero")
+    if ctype == np.complex64:
+        assert lost.mean() > 0.5
+    got = host(G.lmme(dev(A), dev(B), flags=LMME_EXACT))
+    compare(got, re, sg, kap, name=f"lmme exact {np.dtype(ctype).name}", max_ill_fraction=0.02)
+    # benign data: everything certifies, the repair pass changes nothing
+    A2 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 27, 7, 2 * 64 * 64).reshape(2, 64, 64))
+    B2 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 28, 8, 2 * 64 * 64).reshape(2, 64, 64))
+    assert np.array_equal(host(G.lmme(dev(A2), dev(B2), flags=LMME_EXACT)).view(np.uint32),
+                          host(G.lmme(dev(A2), dev(B2), flags=LMME_FAST)).view(np.uint32))
+
+
 # -------------------------------------------------------------------------------- scan
 
 def run_scan_case(G, oracle, T, d, chunk_len, m=None, batch=1, seed=0, dtype=np.float32, name=""):
