@@ -166,6 +166,8 @@ def main():
             "sample": f"first {S} steps of the same chain (definitional log-sum-exp scan in double), {cpu_s:.1f} s",
         }
         # the GPU result on the sampled prefix must agree with the oracle
+        step()  # the copy timed above overwrote the outputs
+        torch.cuda.synchronize()
         got = out[:S].cpu().numpy()
         well = np.isfinite(re)
         err = np.abs(got.real.astype(np.float64) - re)[well]

@@ -133,3 +133,41 @@ def recurrence_inputs(seed: int, batch: int, T: int, d: int, gain: float = 1.05,
     with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
         list(ex.map(fill, range(batch)))
     return A, b
+
+
+# ------------------------------------------------------------------ device-side draws
+# The full-size workloads (tens of GB) are drawn on the GPU by torch's seeded generator; the
+# slices the CPU oracle needs are copied to the host, so both sides still see the same bits.
+
+def device_generator(seed: int, device):
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    return gen
+
+
+def device_normal_blocks(seed: int, n_items: int, item_shape, device, block_items: int, scale: float = 1.0):
+    """Yield (first_item, float32 tensor [k, *item_shape]) blocks of i.i.d. N(0, scale^2) draws
+    covering items [0, n_items); the sequence is a pure function of (seed, block_items)."""
+    import torch
+    gen = device_generator(seed, device)
+    for i0 in range(0, n_items, block_items):
+        k = min(block_items, n_items - i0)
+        x = torch.randn((k,) + tuple(item_shape), dtype=torch.float32, device=device, generator=gen)
+        if scale != 1.0:
+            x.mul_(scale)
+        yield i0, x
+
+
+def device_wide_range_gooms(seed: int, shape, sigma: float, ctype, device):
+    """GOOM tensor with log-magnitudes N(0, sigma^2) and phases 0 or pi with probability 1/2."""
+    import math
+    import torch
+    gen = device_generator(seed, device)
+    comp = torch.float32 if ctype == torch.complex64 else torch.float64
+    z = torch.empty(tuple(shape), dtype=ctype, device=device)
+    zr = torch.view_as_real(z)
+    zr[..., 0] = torch.randn(tuple(shape), dtype=comp, device=device, generator=gen) * sigma
+    zr[..., 1] = (torch.rand(tuple(shape), dtype=torch.float32, device=device, generator=gen) < 0.5).to(comp) * \
+        torch.tensor(math.pi, dtype=comp).item()
+    return z
