@@ -31,7 +31,9 @@ def main():
                     help="leading steps of the chain the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs")
-    ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="time the headline scan only")
+    ap.add_argument("--basic-extras", action="store_true",
+                    help="besides the scan, time only a plain device copy of the same size (for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -101,10 +103,16 @@ def main():
     else:
         alg_bytes = T * 8 * d * d
     achieved_gbs = alg_bytes / (kern_avg[dominant] * 1e-3) / 1e9
+    # HBM bytes per launch of that kernel from the FETCH_SIZE / WRITE_SIZE counter runs on this
+    # workload (64.02 KiB per product for the fix-up kernel at d = 64, default chunking: FETCH_SIZE
+    # scaled by 2 and WRITE_SIZE by 1, the factors a plain copy of known size gives)
+    traffic = args.traffic_bytes
+    if traffic is None and d == 64 and args.chunk_len == 0 and dominant.endswith("fixup_outputs"):
+        traffic = round(T * 64.02 * 1024)
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-        "traffic": args.traffic_bytes, "algorithmic_bytes_per_launch": alg_bytes,
+        "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
         "avg_launch_ms": round(kern_avg[dominant], 4),
     }
     # matrix-core work actually executed: one d^3 product per matrix in phase 1, one per chunk in
@@ -130,7 +138,7 @@ def main():
     }
 
     # ---- extras: the reduction variant (final product only), same input
-    if not args.no_extras:
+    if not args.no_extras and not args.basic_extras:
         fin = torch.empty((d, d), dtype=torch.complex64, device=dev)
         g.reduce(z, chunk_len=args.chunk_len, out=fin)
         torch.cuda.synchronize()
@@ -141,6 +149,7 @@ def main():
         rms = (time.perf_counter() - r0) / 3 * 1e3
         result["reduce"] = {"ms": round(rms, 4), "products_per_s": round(T / (rms * 1e-3), 1),
                             "hbm_gbs": round(T * 8 * d * d / (rms * 1e-3) / 1e9, 1)}
+    if not args.no_extras:
         result["to_goom_gbs"] = round(z.numel() * 12 / t_codec / 1e9, 1)
         # what this machine's HBM sustains for a plain device-to-device copy of the same size
         # (read + write bytes over time): the practical ceiling beside the published 8 TB/s
@@ -152,6 +161,12 @@ def main():
         torch.cuda.synchronize()
         cms = (time.perf_counter() - c0) / 3
         result["hbm_copy_gbs"] = round(2 * z.numel() * 8 / cms / 1e9, 1)
+
+    # ---- the other workloads of the same path, each timed on its own (not part of `value`)
+    if not args.no_extras and not args.basic_extras:
+        del out
+        torch.cuda.empty_cache()
+        result["other_workloads"] = other_workloads(g, torch, dev)
 
     # ---- CPU oracle on a bounded sample of the same workload (reported, not a target)
     if args.cpu_sample_steps > 0:
@@ -166,15 +181,116 @@ def main():
             "sample": f"first {S} steps of the same chain (definitional log-sum-exp scan in double), {cpu_s:.1f} s",
         }
         # the GPU result on the sampled prefix must agree with the oracle
-        step()  # the copy timed above overwrote the outputs
-        torch.cuda.synchronize()
-        got = out[:S].cpu().numpy()
+        got = g.scan(z[:S]).cpu().numpy()
         well = np.isfinite(re)
         err = np.abs(got.real.astype(np.float64) - re)[well]
         tol = np.maximum(1e-3, 1e-4 * np.abs(re[well]))
         result["cpu_baseline"]["gpu_entries_within_tolerance"] = round(float(np.mean(err <= tol)), 6)
 
     print(json.dumps(result), flush=True)
+
+
+def timed(torch, fn, reps=3):
+    fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / reps
+
+
+def kernel_times(g, fn):
+    g.profile_enable(True)
+    fn()
+    per = {}
+    for label, ms in g.profile_records():
+        per[label] = round(per.get(label, 0.0) + ms, 4)
+    g.profile_enable(False)
+    return per
+
+
+def other_workloads(g, torch, dev):
+    """Scan of 128 x 128 matrices, batched LMME, Lyapunov spectrum, non-diagonal recurrence, tiny scan."""
+    import math
+    import synthetic_inputs as si
+    from paper_2510_03426_amd import LMME_EXACT, LMME_FAST
+    res = {}
+
+    # tiny scan (T = 256, d = 8): latency of one call
+    zt = g.to_goom(torch.randn((256, 8, 8), device=dev, generator=si.device_generator(11, dev)))
+    res["scan_T256_d8"] = {"us_per_scan": round(timed(torch, lambda: g.scan(zt), 50) * 1e6, 1)}
+
+    # scan of 128 x 128 matrices, T = 262,144 (same bytes as the headline workload)
+    T, d = 1 << 18, 128
+    z = torch.empty((T, d, d), dtype=torch.complex64, device=dev)
+    for t0, x in si.device_normal_blocks(251003426 * 10 + 3, T, (d, d), dev, 1 << 14):
+        g.to_goom(x, out=z[t0:t0 + x.shape[0]])
+    out = torch.empty_like(z)
+    sec = timed(torch, lambda: g.scan(z, out=out))
+    fl = 2.0 * d ** 3 * 2 * T
+    res["scan_T262144_d128"] = {
+        "ms": round(sec * 1e3, 3), "products_per_s": round(T / sec, 1),
+        "lmme_tflops_executed": round(fl / sec / 1e12, 2),
+        "pct_of_fp32_mfma_peak": round(100 * fl / sec / 1e12 / MFMA_F32_PEAK_TFLOPS, 2),
+        "kernels_ms": kernel_times(g, lambda: g.scan(z, out=out))}
+    del z, out
+    torch.cuda.empty_cache()
+
+    # batched LMME: 8192 pairs of 128 x 128, log-magnitudes N(0, 200^2)
+    B, n = 8192, 128
+    for ctype, name in ((torch.complex64, "c64"), (torch.complex128, "c128")):
+        a = si.device_wide_range_gooms(251003426 * 10 + 31, (B, n, n), 200.0, ctype, dev)
+        b = si.device_wide_range_gooms(251003426 * 10 + 32, (B, n, n), 200.0, ctype, dev)
+        c = torch.empty_like(a)
+        peak = MFMA_F32_PEAK_TFLOPS if name == "c64" else 78.6
+        for flags, fname in ((LMME_FAST, "scaled_product"), (LMME_EXACT, "with_repair")):
+            sec = timed(torch, lambda: g.lmme(a, b, flags=flags, out=c))
+            res[f"lmme_{name}_{fname}"] = {
+                "ms": round(sec * 1e3, 3), "pairs_per_s": round(B / sec, 1),
+                "tflops": round(2.0 * n ** 3 * B / sec / 1e12, 2),
+                "pct_of_mfma_peak": round(100 * 2.0 * n ** 3 * B / sec / 1e12 / peak, 2),
+                "hbm_gbs": round(3 * a.numel() * a.element_size() / sec / 1e9, 1)}
+        # benign range (entries N(0,1)): nothing to repair
+        a = g.to_goom(torch.randn((B, n, n), device=dev, dtype=torch.float32 if name == "c64" else torch.float64))
+        b = g.to_goom(torch.randn((B, n, n), device=dev, dtype=torch.float32 if name == "c64" else torch.float64))
+        sec = timed(torch, lambda: g.lmme(a, b, flags=LMME_FAST, out=c))
+        res[f"lmme_{name}_unit_normal"] = {
+            "ms": round(sec * 1e3, 3), "tflops": round(2.0 * n ** 3 * B / sec / 1e12, 2),
+            "pct_of_mfma_peak": round(100 * 2.0 * n ** 3 * B / sec / 1e12 / peak, 2),
+            "hbm_gbs": round(3 * a.numel() * a.element_size() / sec / 1e9, 1)}
+        del a, b, c
+        torch.cuda.empty_cache()
+
+    # Lyapunov spectrum of Lorenz-96 (d = 32) over T = 131,072 Jacobians, resets every 32 steps
+    T, d = 131072, 32
+    Jr, _ = si.lorenz96_jacobians(si.BASE_SEED + 4, T, d=d, burn_in=10000)
+    Jz = g.to_goom(torch.from_numpy(Jr).to(dev))
+    sec = timed(torch, lambda: g.lyapunov_spectrum(Jz, 0.01))
+    lam = g.lyapunov_spectrum(Jz, 0.01).cpu().numpy()
+    res["lyapunov_lorenz96_d32_T131072"] = {
+        "ms": round(sec * 1e3, 3), "jacobians_per_s": round(T / sec, 1), "lambda_1": round(float(lam[0]), 4),
+        "kernels_ms": kernel_times(g, lambda: g.lyapunov_spectrum(Jz, 0.01))}
+    sec = timed(torch, lambda: g.scan_reset(Jz))
+    res["reset_scan_all_states_d32_T131072"] = {
+        "ms": round(sec * 1e3, 3), "jacobians_per_s": round(T / sec, 1),
+        "kernels_ms": kernel_times(g, lambda: g.scan_reset(Jz))}
+    del Jz
+
+    # non-diagonal recurrence: 8 x 16 sequences of 65,536 tokens, d = 32
+    nseq, T, d = 128, 65536, 32
+    az = torch.empty((nseq, T, d, d), dtype=torch.complex64, device=dev)
+    for s0, x in si.device_normal_blocks(251003426 * 10 + 51, nseq, (T, d, d), dev, 4, scale=1.05 / math.sqrt(d)):
+        g.to_goom(x, out=az[s0:s0 + x.shape[0]])
+    bz = g.to_goom(torch.randn((nseq, T, d), device=dev, generator=si.device_generator(251003426 * 10 + 52, dev)))
+    h = torch.empty((nseq, T, d), dtype=torch.complex64, device=dev)
+    sec = timed(torch, lambda: g.affine_scan(az, bz, out=h))
+    byts = (az.numel() + bz.numel() + h.numel()) * 8
+    res["recurrence_128seq_T65536_d32"] = {
+        "ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1),
+        "hbm_gbs_algorithmic": round(byts / sec / 1e9, 1), "pct_of_hbm_peak": round(100 * byts / sec / 1e9 / HBM_PEAK_GBS, 2),
+        "kernels_ms": kernel_times(g, lambda: g.affine_scan(az, bz, out=h))}
+    return res
 
 
 if __name__ == "__main__":
