@@ -1,0 +1,230 @@
+// Linear recurrence with bias, h_t = A_t h_{t-1} + b_t over GOOMs (paper Section 4.3), float
+// components: the two kernels its long batched form spends its time in.
+//
+//   * chunk products of the augmented matrices [A | b] (last row implicit): the hot chain
+//     kernel with one more wave for the bias column;
+//   * the walk that turns the carried vectors into all states: per chunk, h <- A_t h + b_t as a
+//     matrix-vector product.  One wave owns one chunk.  A lane loads four adjacent entries of a
+//     row of A_t (so d / 4 lanes share a row and 256 / d rows are handled per pass), scales
+//     them by the row's power-of-two shift, multiplies by the vector's mantissas and adds up
+//     across the row's lanes.  The vector is kept as float mantissas with one exponent for
+//     the whole vector; it goes from the lanes that own rows to the lanes that own columns
+//     through a few words of LDS private to the wave.  Nothing but A_t, b_t (read once) and
+//     h_t (written once) touches HBM, which bounds this kernel.
+#include "goom_chain_fast.h"
+
+namespace goom_chain {
+
+namespace {
+
+
+template <int CTRL> __device__ inline float add_dpp(float x)
+{
+    const int y = __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true);
+    return x + __builtin_bit_cast(float, y);
+}
+
+constexpr int kWalkWaves = 4; // chunks per workgroup
+
+template <int DP> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk_kernel(ChainArgs a, long long nchains)
+{
+    typedef Comp<float> C;
+    constexpr int LPR = DP / 4;   // lanes that share a row
+    constexpr int RPP = 64 / LPR; // rows per pass
+    constexpr int Q = DP / RPP;   // passes
+    __shared__ __align__(16) float hvec_all[kWalkWaves][DP];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const long long chain = (long long)blockIdx.x * kWalkWaves + wave;
+    if (chain >= nchains) return; // whole wave; the kernel has no workgroup barrier
+    float *hvec = hvec_all[wave];
+    const int rsub = lane / LPR;
+    const int c4 = 4 * (lane % LPR);
+    const bool row_owner = (lane % LPR) == 0;
+
+    const long long item = chain / a.chunks_launched;
+    const long long chunk = chain % a.chunks_launched;
+    const long long t0 = chunk * a.chunk_len;
+    long long len = a.steps - t0;
+    if (len > a.chunk_len) len = a.chunk_len;
+    if (len <= 0) return;
+    const unsigned char *left0 = a.left + item * a.left_batch_stride + t0 * a.left_step_stride;
+    const float *bias0 = reinterpret_cast<const float *>(a.bias) + (size_t)(item * a.steps + t0) * DP * 2;
+    float *out0 = reinterpret_cast<float *>(a.out_goom) + (size_t)(item * a.steps + t0) * DP * 2;
+
+    // carried vector: column 0 of a factored state
+    long long iidx = item * a.chunks_per_item + chunk;
+    if (a.init_group > 0) {
+        long long grp = chunk / a.init_group;
+        if (grp >= a.init_ngroups) grp = a.init_ngroups - 1;
+        iidx = (item * a.init_ngroups + grp) * (a.init_group + 1) + (chunk - grp * a.init_group);
+    }
+    const unsigned char *ip = a.init + iidx * a.init_stride;
+    const float *mp = reinterpret_cast<const float *>(ip);
+    double eh = *reinterpret_cast<const double *>(ip + (size_t)DP * a.fact_cols * sizeof(float));
+    f4 hm;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) hm[e] = mp[(size_t)(c4 + e) * a.fact_cols];
+    {   // a zero vector carries no meaningful exponent
+        const bool nz = hm[0] != 0.0f || hm[1] != 0.0f || hm[2] != 0.0f || hm[3] != 0.0f;
+        if (__builtin_amdgcn_ballot_w64(nz) == 0 || !(__builtin_fabs(eh) < 1.0e15)) eh = 0.0;
+    }
+
+    Item4 cur[Q], nxt[Q];
+    float2 bcur[Q], bnxt[Q];
+    auto load_step = [&](long long t, Item4 (&it)[Q], float2 (&bb)[Q]) {
+        const float *src = reinterpret_cast<const float *>(left0 + t * a.left_step_stride);
+        const float *bsrc = bias0 + (size_t)t * DP * 2;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const int row = q * RPP + rsub;
+            const f4 *gp = reinterpret_cast<const f4 *>(src + ((size_t)row * DP + c4) * 2);
+            it[q].a = gp[0];
+            it[q].b = gp[1];
+            bb[q] = *reinterpret_cast<const float2 *>(bsrc + (size_t)row * 2);
+        }
+    };
+    load_step(0, cur, bcur);
+
+    const float kHi = 1.44269502162933349609375f; // float nearest log2(e)
+    const float kLo = 1.925963033500011e-8f;      // log2(e) - kHi
+    for (long long t = 0; t < len; ++t) {
+        load_step(t + 1 < len ? t + 1 : len - 1, nxt, bnxt);
+        const float eh_f = (float)eh;
+        float val[Q], nrow[Q], barg[Q];
+        float bmax = -1.0e30f;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const float re[4] = {cur[q].a[0], cur[q].a[2], cur[q].b[0], cur[q].b[2]};
+            const float im[4] = {cur[q].a[1], cur[q].a[3], cur[q].b[1], cur[q].b[3]};
+            // row shift: a whole number near the row's largest log2|A_ij|
+            float u = vmax_raw(vmax_raw(re[0], re[1]), vmax_raw(re[2], re[3])) * kHi;
+            int key = C::key_of(u);
+            key = C::imax(key, C::dpp<0xB1>(key));
+            key = C::imax(key, C::dpp<0x4E>(key));
+            if (LPR >= 8) key = C::imax(key, C::dpp<0x141>(key));
+            if (LPR >= 16) key = C::imax(key, C::dpp<0x140>(key));
+            const float mx = C::of_key(key);
+            const bool zero_row = !(mx > -1.0e30f);
+            const float n = zero_row ? 0.0f : __builtin_ceilf(mx);
+            const float nsub = zero_row ? __builtin_huge_valf() : n;
+            float part = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                // (this kernel waits on memory, so the entries get the exponential that is good to
+                // a few units in the last place at any shift rather than the cheapest one)
+                const float v = C::exp2_shifted(re[e], nsub);
+                const float kf = __builtin_fmaf(im[e], 0.318309886183790671538f, 12582912.0f);
+                const float sv = __builtin_bit_cast(float, __builtin_bit_cast(int, v) ^ (__builtin_bit_cast(int, kf) << 31));
+                part = __builtin_fmaf(sv, hm[e], part);
+            }
+            part = add_dpp<0xB1>(part);
+            part = add_dpp<0x4E>(part);
+            if (LPR >= 8) part = add_dpp<0x141>(part);
+            if (LPR >= 16) part = add_dpp<0x140>(part);
+            // the row's entry of A_t h is part 2^(n + eh); the bias joins it on that scale
+            float x = __builtin_fmaf(bcur[q].x, kHi, -(n + eh_f));
+            x = __builtin_fmaf(bcur[q].x, kLo, x);
+            val[q] = part;
+            nrow[q] = n;
+            barg[q] = x;
+            bmax = C::max_(bmax, x);
+        }
+        // should the vector have shrunk so far below the bias that the bias would overflow on
+        // its scale, the vector is scaled down first (to nothing, if need be)
+        bmax = C::template group_allmax<64>(bmax, bmax);
+        const float down = C::max_(0.0f, __builtin_ceilf(bmax) - 64.0f);
+        const int idown = -(int)C::clamp_shift(down);
+        const float ecur_f = eh_f + down;
+        float xmax = -1.0e30f;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const float bv = C::apply_sign(__builtin_amdgcn_exp2f(barg[q] - down), bcur[q].y);
+            val[q] = __builtin_ldexpf(val[q], idown) + bv;
+            if (row_owner) {
+                const float re = C::out_re_f(val[q], nrow[q] + ecur_f);
+                const float im = val[q] < 0.0f ? C::pi() : 0.0f;
+                *reinterpret_cast<float2 *>(out0 + ((size_t)t * DP + q * RPP + rsub) * 2) = float2{re, im};
+            }
+            const float ex = val[q] != 0.0f ? C::exponent_of(val[q]) + nrow[q] : -1.0e30f;
+            xmax = C::max_(xmax, ex);
+        }
+        // new exponent of the vector: the largest entry's; mantissas at most 1 in magnitude
+        {
+            int key = C::key_of(xmax);
+            if (LPR < 8) key = C::imax(key, C::dpp<0x141>(key));
+            if (LPR < 16) key = C::imax(key, C::dpp<0x140>(key));
+            key = C::xor16_imax(key);
+            key = C::xor32_imax(key);
+            xmax = C::of_key(key);
+        }
+        const bool all_zero = !(xmax > -1.0e29f);
+        const float xm = all_zero ? 0.0f : xmax;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const float m = __builtin_ldexpf(val[q], (int)C::clamp_shift(nrow[q] - xm));
+            if (row_owner) hvec[q * RPP + rsub] = m;
+        }
+        eh = all_zero ? 0.0 : eh + (double)down + (double)xm;
+        // rows to columns through the wave's own LDS words (a wave's LDS operations complete in order)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        hm = *reinterpret_cast<const f4 *>(&hvec[c4]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            cur[q] = nxt[q];
+            bcur[q] = bnxt[q];
+        }
+    }
+}
+
+template <int DP> int launch_walk(goom_ctx *ctx, const ChainArgs &args, long long nchains, const char *label)
+{
+    const long long grid = (nchains + kWalkWaves - 1) / kWalkWaves;
+    if (grid <= 0) return GOOM_OK;
+    if (grid > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many chains for one launch (%lld)", nchains);
+    goom::prof_begin(ctx, label);
+    hipLaunchKernelGGL(affine_walk_kernel<DP>, dim3((unsigned)grid), dim3(kWalkWaves * 64), 0, ctx->stream, args, nchains);
+    goom::prof_end(ctx);
+    return goom::check_hip(ctx, hipGetLastError(), "launch affine_walk_kernel");
+}
+
+} // namespace
+
+// chunk products with the bias wave: the factor fills its tile, the state is [A* | b*] with the
+// bias in column d, starting from the identity, and only the chunk's factored product is wanted
+bool affine_chunk_applies(const ChainArgs &args, int dp)
+{
+    return (dp == 16 || dp == 32 || dp == 64) && args.n == dp && args.d == dp && args.m == dp + 1 && args.bias_mode == 1 &&
+           args.bias_col == dp && args.init_mode == 0 && args.out_goom == nullptr && args.out_fact_steps == nullptr &&
+           args.out_fact_final != nullptr && args.fact_cols == dp + 16;
+}
+
+int dispatch_affine_chunk(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label)
+{
+    switch (dp) {
+    case 16: return launch_fast<16, 1, true>(ctx, args, grid, label);
+    case 32: return launch_fast<32, 2, true>(ctx, args, grid, label);
+    default: return launch_fast<64, 4, true>(ctx, args, grid, label);
+    }
+}
+
+// the walk: a single state column that receives the bias, started from factored carries,
+// every state stored as GOOMs
+bool affine_walk_applies(const ChainArgs &args, int dp)
+{
+    return (dp == 16 || dp == 32) && args.n == dp && args.d == dp && args.m == 1 && args.bias_mode == 1 && args.bias_col == 0 &&
+           args.init_mode == 1 && args.out_goom != nullptr && !args.out_goom_last_only && args.out_fact_steps == nullptr &&
+           args.out_fact_final == nullptr;
+}
+
+int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long nchains, const char *label)
+{
+    return dp == 16 ? launch_walk<16>(ctx, args, nchains, label) : launch_walk<32>(ctx, args, nchains, label);
+}
+
+} // namespace goom_chain

@@ -5,6 +5,8 @@ namespace goom_chain {
 int dispatch_f32_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label)
 {
     if (fast_applies(args, dp, nw)) return dispatch_fast(ctx, args, dp, grid, label);
+    if (affine_chunk_applies(args, dp)) return dispatch_affine_chunk(ctx, args, dp, grid, label);
+    if (affine_walk_applies(args, dp)) return dispatch_affine_walk(ctx, args, dp, grid, label);
     return dispatch<float, 0>(ctx, args, dp, nw, grid, label);
 }
 } // namespace goom_chain

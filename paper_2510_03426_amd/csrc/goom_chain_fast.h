@@ -1,7 +1,10 @@
 // Hot variant of the chain kernel: float components, left factors given as GOOMs that
-// fill the padded tile exactly (d = 16, 32, 64 or 128), state of 16 * NW columns, no bias.
+// fill the padded tile exactly (d = 16, 32, 64 or 128), state of 16 * NW columns.
 // This is the kernel the long scans spend their time in (phase 1 and phase 3 of the
 // three-phase scan; paper Section 4.1), and LMME on such shapes (Section 3.2).
+// With BIAS one more wave carries column d of the augmented state [A* | b*] of a linear
+// recurrence with bias (Section 4.3): it takes no part in converting the factor, runs the
+// same matrix instructions on its slab, and adds the step's bias vector to its column.
 //
 // On this chip the float matrix instructions run at the rate of the vector ALU and do
 // not overlap with it, so a step costs (matrix cycles) + 4 x (vector instructions) and
@@ -33,14 +36,15 @@ __device__ inline float vmax_raw(float x, float y)
     return r;
 }
 
-template <int DP, int NW>
-__global__ __launch_bounds__(NW * 64, (DP <= 64 ? 2 : 1)) void chain_kernel_fast(ChainArgs a)
+template <int DP, int NW, bool BIAS>
+__global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) void chain_kernel_fast(ChainArgs a)
 {
     typedef Comp<float> C;
     constexpr int KT = DP / 16;
     constexpr int LDA = DP + 4;
-    constexpr int M = 16 * NW;   // state columns
-    constexpr int NT = NW * 64;
+    constexpr int NWT = NW + (BIAS ? 1 : 0); // waves, one per 16-column slab of the state
+    constexpr int M = 16 * NWT;  // state columns
+    constexpr int NT = NW * 64;  // threads that convert the factor
     constexpr int LPR = DP / 4;  // lanes per row of the factor
     constexpr int NITEMS = DP * LPR;
     constexpr int Q = NITEMS / NT; // items per thread
@@ -61,6 +65,8 @@ __global__ __launch_bounds__(NW * 64, (DP <= 64 ? 2 : 1)) void chain_kernel_fast
     const int c = lane & 15;
     const int col = wave * 16 + c;
     const int c4 = 4 * (tid % LPR); // first of this lane's four factor columns
+    const bool converter = !BIAS || wave < NW;
+    const bool bias_wave = BIAS && wave == NW;
 
     const long long chain = blockIdx.x;
     const long long item = chain / a.chunks_launched;
@@ -110,7 +116,8 @@ __global__ __launch_bounds__(NW * 64, (DP <= 64 ? 2 : 1)) void chain_kernel_fast
             // a row that is entirely zero keeps a finite (hugely negative) shift, and its
             // exponent arguments are forced to -inf so that nothing can overflow
             const bool zero_row = !(mx > -1.0e30f);
-            const float n = zero_row ? -1.0e30f : __builtin_ceilf(mx);
+            // (with a bias column the shift of such a row must stay small: the bias is scaled by it)
+            const float n = zero_row ? (BIAS ? 0.0f : -1.0e30f) : __builtin_ceilf(mx);
             const float nsub = zero_row ? __builtin_huge_valf() : n;
             f4 y;
 #pragma unroll
@@ -172,11 +179,22 @@ __global__ __launch_bounds__(NW * 64, (DP <= 64 ? 2 : 1)) void chain_kernel_fast
     }
 
     Item4 pre[Q];
-    if (len > 0) {
+    if (len > 0 && converter) {
         load_items(0, pre);
         convert_items(pre, 0, nullptr);
         load_items(len > 1 ? 1 : 0, pre);
     }
+    // bias vector of a step, rows 16 kt + 4 g + v of this lane: (re, im) pairs, two 16-byte loads per kt
+    f4 bpre[BIAS ? KT : 1][2];
+    auto load_bias = [&](long long t) {
+        const float *bp = reinterpret_cast<const float *>(a.bias) + ((size_t)(item * a.steps + t0 + t) * DP + 4 * g) * 2;
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            bpre[kt][0] = *reinterpret_cast<const f4 *>(bp + (size_t)kt * 32);
+            bpre[kt][1] = *reinterpret_cast<const f4 *>(bp + (size_t)kt * 32 + 4);
+        }
+    };
+    if (BIAS && bias_wave && len > 0) load_bias(0);
     __syncthreads();
 
     for (long long t = 0; t < len; ++t) {
@@ -202,8 +220,46 @@ __global__ __launch_bounds__(NW * 64, (DP <= 64 ? 2 : 1)) void chain_kernel_fast
         }
         // Past the end of the chain the last factor is converted and loaded once more
         // (clamped index) rather than branching; nobody reads the result.
-        convert_items(pre, cur ^ 1, nsh);
-        load_items(t + 2 < len ? t + 2 : len - 1, pre);
+        if (converter) {
+            convert_items(pre, cur ^ 1, nsh);
+            load_items(t + 2 < len ? t + 2 : len - 1, pre);
+        }
+        if (BIAS && bias_wave) {
+            // b_i enters entry (i, d) of the product, which is held as acc 2^(n_i + ecol): add
+            // (+-) 2^(log2|b_i| - n_i - ecol).  Should the column have shrunk so far below the bias
+            // that this would overflow, the column is first scaled down (to nothing, if need be).
+            const float kHi = 1.44269502162933349609375f;
+            const float kLo = 1.925963033500011e-8f;
+            const float ecol_f = (float)ecol;
+            float arg[KT][4];
+            float amax = -1.0e30f;
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                const f4 nv = *reinterpret_cast<const f4 *>(&nsh[16 * mt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float re = bpre[mt][v >> 1][(v & 1) * 2];
+                    float x = __builtin_fmaf(re, kHi, -(nv[v] + ecol_f));
+                    x = __builtin_fmaf(re, kLo, x);
+                    arg[mt][v] = x;
+                    amax = C::max_(amax, x);
+                }
+            }
+            amax = C::xor16_32_max(amax);
+            const float down = C::max_(0.0f, __builtin_ceilf(amax) - 64.0f);
+            const int idown = -(int)C::clamp_shift(down);
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float im = bpre[mt][v >> 1][(v & 1) * 2 + 1];
+                    const float bv = C::apply_sign(__builtin_amdgcn_exp2f(arg[mt][v] - down), im);
+                    const float sum = __builtin_ldexpf(acc[mt][v], idown) + bv;
+                    acc[mt][v] = c == 0 ? sum : acc[mt][v];
+                }
+            if (c == 0) ecol += (double)down;
+            load_bias(t + 1 < len ? t + 1 : len - 1);
+        }
 
         // ------------------------------------------------------------ outputs
         // entry (i = 16 mt + 4 g + v, col) of the product is acc 2^(n_i + ecol)
@@ -279,7 +335,9 @@ __global__ __launch_bounds__(NW * 64, (DP <= 64 ? 2 : 1)) void chain_kernel_fast
 #pragma unroll
             for (int v = 0; v < 4; ++v) cm = C::max_(cm, __builtin_fabsf(st[kt][v]));
         cm = C::xor16_32_max(cm);
-        double ev = cm > 0.0f ? ecol : kNegBig;
+        // (the bias column is not contracted over when the product serves as a left factor: it
+        // keeps an exponent of its own, so a bias far above or below A* costs neither any bits)
+        double ev = (cm > 0.0f && !bias_wave) ? ecol : kNegBig;
 #pragma unroll
         for (int s = 1; s < 16; s <<= 1) {
             const double o = shfl_xor_double(ev, s);
@@ -288,25 +346,25 @@ __global__ __launch_bounds__(NW * 64, (DP <= 64 ? 2 : 1)) void chain_kernel_fast
         if (lane == 0) wave_red[wave] = ev;
         __syncthreads();
         double emax = kNegBig;
-        for (int w = 0; w < NW; ++w) emax = wave_red[w] > emax ? wave_red[w] : emax;
+        for (int w = 0; w < NWT; ++w) emax = wave_red[w] > emax ? wave_red[w] : emax;
         if (emax == kNegBig) emax = 0.0;
         double dsh = ecol - emax;
         dsh = dsh > -4000.0 ? dsh : -4000.0;
-        const int shift = cm > 0.0f ? (int)dsh : 0;
+        const int shift = (cm > 0.0f && !bias_wave) ? (int)dsh : 0;
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
             for (int v = 0; v < 4; ++v)
                 mp[(size_t)(16 * kt + 4 * g + v) * a.fact_cols + col] = __builtin_ldexpf(st[kt][v], shift);
-        if (g == 0) ep[col] = emax;
+        if (g == 0) ep[col] = bias_wave ? ecol : emax;
     }
 }
 
-template <int DP, int NW> int launch_fast(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
+template <int DP, int NW, bool BIAS> int launch_fast(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
 {
     constexpr int LDA = DP + 4;
-    const size_t lds = 2 * ((size_t)DP * LDA * sizeof(float) + (size_t)DP * sizeof(float)) + 64;
-    auto kern = chain_kernel_fast<DP, NW>;
+    const size_t lds = 2 * ((size_t)DP * LDA * sizeof(float) + (size_t)DP * sizeof(float)) + 128;
+    auto kern = chain_kernel_fast<DP, NW, BIAS>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return goom::check_hip(ctx, e, "hipFuncSetAttribute(chain_kernel_fast)");
@@ -314,7 +372,7 @@ template <int DP, int NW> int launch_fast(goom_ctx *ctx, const ChainArgs &args, 
     if (grid <= 0) return GOOM_OK;
     if (grid > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many chains for one launch (%lld)", grid);
     goom::prof_begin(ctx, label);
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds, ctx->stream, args);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((NW + (BIAS ? 1 : 0)) * 64), lds, ctx->stream, args);
     goom::prof_end(ctx);
     return goom::check_hip(ctx, hipGetLastError(), "launch chain_kernel_fast");
 }
@@ -327,13 +385,21 @@ inline bool fast_applies(const ChainArgs &args, int dp, int nw)
            ((dp == 16 && nw == 1) || (dp == 32 && nw == 2) || (dp == 64 && nw == 4) || (dp == 128 && nw == 8));
 }
 
+// Kernels of the linear recurrence with bias (separate translation unit): chunk products of
+// the augmented matrices with the extra bias wave, and the matrix-vector walk that produces
+// the states from the carried vectors.
+bool affine_chunk_applies(const ChainArgs &args, int dp);
+int dispatch_affine_chunk(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label);
+bool affine_walk_applies(const ChainArgs &args, int dp);
+int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label);
+
 inline int dispatch_fast(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label)
 {
     switch (dp) {
-    case 16: return launch_fast<16, 1>(ctx, args, grid, label);
-    case 32: return launch_fast<32, 2>(ctx, args, grid, label);
-    case 64: return launch_fast<64, 4>(ctx, args, grid, label);
-    default: return launch_fast<128, 8>(ctx, args, grid, label);
+    case 16: return launch_fast<16, 1, false>(ctx, args, grid, label);
+    case 32: return launch_fast<32, 2, false>(ctx, args, grid, label);
+    case 64: return launch_fast<64, 4, false>(ctx, args, grid, label);
+    default: return launch_fast<128, 8, false>(ctx, args, grid, label);
     }
 }
 

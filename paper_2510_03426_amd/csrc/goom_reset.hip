@@ -18,10 +18,10 @@
 // triangular factors taken at the resets: triangular factors multiply, so their diagonals
 // accumulate exactly as in the step-by-step method).
 //
-// One workgroup of 256 threads; everything lives in LDS; float arithmetic with double
-// accumulation of the logarithms.  The chain of chunks is inherently serial (each reset
-// depends on the previous one), so this phase is latency bound; it is small next to the
-// streaming phases as long as the chunk count stays in the hundreds.
+// One wave per batch item, matrices in registers, float arithmetic with double accumulation
+// of the logarithms.  The chain of chunks is inherently serial (each reset depends on the
+// previous one), so this phase is latency bound: what counts is the length of the dependent
+// instruction chain per chunk, which is why it runs without a single workgroup barrier.
 #include "goom_internal.h"
 
 namespace {
@@ -47,240 +47,387 @@ struct ResetArgs {
     float cos_threshold;
 };
 
-__device__ inline float warp_sum(float v)
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+__device__ inline f4 mfma4(float x, float y, f4 acc) { return __builtin_amdgcn_mfma_f32_16x16x4f32(x, y, acc, 0, 0, 0); }
+
+__device__ inline float read_lane(float v, int lane)
 {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
-    return v;
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
 
-// Column-major d x d matrix in LDS with leading dimension LD = DP + 1.
-template <int DP> struct Lds {
-    static constexpr int LD = DP + 1;
-    float t[DP * LD];   // chunk product (row-major here: t[i * LD + j])
-    float y[DP * LD];   // state, column-major: y[k * LD + i]
-    float z[DP * LD];   // product / work, column-major
-    float rdiag[DP];    // diagonal of R
-    float colscale[DP]; // per-column scalars
-    double yexp[DP];    // power-of-two exponent of every state column
-    double lognorm[DP]; // natural log of every column norm of z (including exponents)
-    int flag;
+// LDS operations of one wave complete in program order; this only keeps the compiler from
+// moving them across the point where lanes hand data to each other.
+__device__ inline void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+typedef double d4 __attribute__((ext_vector_type(4)));
+
+// One wave per batch item.  All DP x DP matrices live in registers in the layout the
+// 16 x 16 x 4 matrix instruction leaves its result in: lane (g = lane / 16, c = lane % 16),
+// register [nt][mt][v] holds entry (row 16 mt + 4 g + v, column 16 nt + c).  That layout is
+// also the instruction's B operand, and, read as "column block first", the A operand of the
+// transpose, so both Z = T Y and the Gram matrix G = Z^T Z run on the matrix unit without
+// moving the state; only the chunk product T goes through LDS (it arrives row by row).
+//
+// QR by the Gram matrix: Cholesky elimination G = R^T R, one column per step, with the same
+// column operations applied to Z, which turns Z into Q = Z R^-1 in place.  Step k scales
+// column k by 1 / sqrt(pivot) and subtracts r_kj times it from every later column j; row k
+// of R and column k of Q reach the other lanes through a few words of LDS.  The pivots are
+// the squares of R's diagonal.  G is formed and eliminated in double (the double-precision
+// matrix instruction; its result has row 16 mt + 4 v + g in register v), so the pivots stay
+// accurate up to cond(Z)^2 of about 1e12; the columns of Z are updated in float, which
+// costs orthogonality in proportion to sqrt(largest ratio of a column's squared norm to its
+// pivot).  When that ratio is large the factorisation is repeated on Q, which restores
+// orthogonality to rounding level, and the two diagonals multiply.
+template <int DP> struct Wave {
+    static constexpr int KT = DP / 16;
+    static constexpr int LDT = DP + 4;
+    float tile[DP * LDT]; // chunk product, row-major, rows padded against bank conflicts
+    double rrow[DP];      // row k of R, entry j at position j
+    double rperm[DP];     // the same with entry 16 mt + 4 v + g at position 16 mt + 4 g + v
+    float qcol[DP];       // column k of Q
+    double diag[DP];      // diagonal of the Gram matrix
 };
 
-// Right-looking modified Gram-Schmidt on the columns of m (column-major, d x d), in place:
-// m <- Q, rdiag <- diag(R) (> 0).  Returns nothing; a zero column stays zero with R_kk = 0.
-template <int DP> __device__ void mgs_sweep(float *m, float *rdiag, float *tmp, int d, int tid)
+// G = Z^T Z in double; G[nt][mt][v] = entry (row 16 mt + 4 v + g, column 16 nt + c)
+template <int DP> __device__ void gram(const f4 (&Z)[DP / 16][DP / 16], d4 (&G)[DP / 16][DP / 16])
 {
-    constexpr int LD = DP + 1;
-    const int lane = tid & 63, wave = tid >> 6;
-    for (int k = 0; k < d; ++k) {
-        // norm of column k (first wave)
-        if (wave == 0) {
-            float v = lane < d ? m[k * LD + lane] : 0.0f;
-            float ss = warp_sum(v * v);
-            float nrm = __builtin_sqrtf(ss);
-            if (lane == 0) rdiag[k] = nrm;
-            if (lane < d) m[k * LD + lane] = nrm > 0.0f ? v / nrm : 0.0f;
+    constexpr int KT = DP / 16;
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) {
+            d4 acc = {0., 0., 0., 0.};
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64((double)Z[mt][kt][v], (double)Z[nt][kt][v], acc, 0, 0, 0);
+            G[nt][mt] = acc;
         }
-        __syncthreads();
-        // r_kj = q_k . a_j for j > k: 8 threads per column j, then a_j -= r_kj q_k
-        const int nrem = d - 1 - k;
-        for (int j0 = 0; j0 < nrem; j0 += kThreads / 8) {
-            const int jj = j0 + (tid >> 3);
-            const int j = k + 1 + jj;
-            const int part = tid & 7;
-            float dot = 0.0f;
-            if (jj < nrem)
-                for (int i = part; i < d; i += 8) dot += m[k * LD + i] * m[j * LD + i];
-            dot += __shfl_xor(dot, 1, 64);
-            dot += __shfl_xor(dot, 2, 64);
-            dot += __shfl_xor(dot, 4, 64);
-            if (jj < nrem && part == 0) tmp[j] = dot;
-        }
-        __syncthreads();
-        for (int e = tid; e < nrem * d; e += kThreads) {
-            const int j = k + 1 + e / d, i = e % d;
-            m[j * LD + i] -= tmp[j] * m[k * LD + i];
-        }
-        __syncthreads();
-    }
 }
 
-template <int DP> __global__ __launch_bounds__(kThreads) void reset_carry_kernel(ResetArgs a)
+// the diagonal of G into s.diag (entry j at position j)
+template <int DP> __device__ void diagonal_to_lds(const d4 (&G)[DP / 16][DP / 16], Wave<DP> &s, int g, int c)
 {
-    constexpr int LD = DP + 1;
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    Lds<DP> &s = *reinterpret_cast<Lds<DP> *>(smem_raw);
-    const int tid = threadIdx.x;
+    constexpr int KT = DP / 16;
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) {
+        // G[j][j] for column j = 16 nt + c: row part c = 4 v + g', so it sits in lane (c % 4, c), register c / 4
+        double dsel = G[nt][nt][0];
+        dsel = (c >> 2) == 1 ? G[nt][nt][1] : dsel;
+        dsel = (c >> 2) == 2 ? G[nt][nt][2] : dsel;
+        dsel = (c >> 2) == 3 ? G[nt][nt][3] : dsel;
+        if (g == (c & 3)) s.diag[16 * nt + c] = dsel;
+    }
+    wave_sync();
+}
+
+// Cholesky elimination on (G, Z); piv[nt] receives the pivot of column 16 nt + c.  Returns the
+// largest ratio G_kk / pivot_k seen (1 for orthogonal columns).
+template <int DP> __device__ float eliminate(d4 (&G)[DP / 16][DP / 16], f4 (&Z)[DP / 16][DP / 16], double (&piv)[DP / 16],
+                                             Wave<DP> &s, int g, int c)
+{
+    constexpr int KT = DP / 16;
+    double g0[KT]; // squared norms of this lane's columns before elimination
+    diagonal_to_lds<DP>(G, s, g, c);
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) g0[nt] = s.diag[16 * nt + c];
+#pragma unroll
+    for (int k = 0; k < DP; ++k) {
+        const int kb = k / 16, ck = k % 16;
+        const int gk = ck % 4, vk = ck / 4; // row k of G: lanes with g == gk, register vk
+        const int gq = ck / 4;              // (rows of Z: row 16 mt + 4 g + v)
+        (void)gq;
+        const double pv = G[kb][kb][vk];
+        const int lo = __builtin_amdgcn_readlane((int)(__builtin_bit_cast(unsigned long long, pv) & 0xffffffffull), 16 * gk + ck);
+        const int hi = __builtin_amdgcn_readlane((int)(__builtin_bit_cast(unsigned long long, pv) >> 32), 16 * gk + ck);
+        const double pivot = __builtin_bit_cast(double, ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
+        const float scf = pivot > 1.0e-30 ? __builtin_amdgcn_rsqf((float)pivot) : 0.0f;
+        // one Newton step takes the float reciprocal square root to double accuracy where it matters
+        const double scd = pivot > 1.0e-30 ? (double)scf * (1.5 - 0.5 * pivot * (double)scf * (double)scf) : 0.0;
+        if (c == ck) piv[kb] = pivot;
+        // row k of R, entries right of the diagonal (zero elsewhere, so finished columns stay put)
+        if (g == gk) {
+#pragma unroll
+            for (int nt = kb; nt < KT; ++nt) {
+                const int j = 16 * nt + c;
+                const double r = j > k ? G[nt][kb][vk] * scd : 0.0;
+                s.rrow[j] = r;
+                s.rperm[(j & ~15) | ((j & 3) << 2) | ((j >> 2) & 3)] = r;
+            }
+        }
+        // column k of Q
+        if (c == ck) {
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                Z[kb][mt] *= (float)scd;
+                *reinterpret_cast<f4 *>(&s.qcol[16 * mt + 4 * g]) = Z[kb][mt];
+            }
+        }
+        wave_sync();
+        double rj[KT];
+#pragma unroll
+        for (int nt = kb; nt < KT; ++nt) rj[nt] = s.rrow[16 * nt + c];
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) {
+            const f4 qi = *reinterpret_cast<const f4 *>(&s.qcol[16 * mt + 4 * g]);
+#pragma unroll
+            for (int nt = kb; nt < KT; ++nt) Z[nt][mt] -= qi * (float)rj[nt];
+        }
+#pragma unroll
+        for (int mt = kb; mt < KT; ++mt) {
+            // this lane's rows of G are 16 mt + 4 v + g, v = 0..3: contiguous in the permuted copy
+            const d4 ri = *reinterpret_cast<const d4 *>(&s.rperm[16 * mt + 4 * g]);
+#pragma unroll
+            for (int nt = kb; nt < KT; ++nt) G[nt][mt] -= ri * rj[nt];
+        }
+        wave_sync();
+    }
+    float worst = 1.0f;
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) {
+        const float ratio = piv[nt] > 1.0e-30 ? (float)(g0[nt] / piv[nt]) : 1.0f;
+        worst = fmaxf(worst, ratio);
+    }
+#pragma unroll
+    for (int sft = 1; sft < 16; sft <<= 1) worst = fmaxf(worst, __shfl_xor(worst, sft, 64));
+    return read_lane(worst, 0); // the same in every lane; this tells the compiler so
+}
+
+template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(ResetArgs a)
+{
+    constexpr int KT = DP / 16;
+    constexpr int LDT = DP + 4;
+    constexpr int TQ = DP * DP / 4 / 64; // 16-byte pieces of the chunk product per lane
+    __shared__ __align__(16) Wave<DP> s;
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, c = lane & 15;
     const int d = a.d;
     const long long b = blockIdx.x;
     const size_t tot_mant = (size_t)DP * a.tot_cols * sizeof(float);
     const size_t car_mant = (size_t)DP * a.car_cols * sizeof(float);
-    double growth_acc = 0.0; // thread k < d accumulates column k
 
-    // ---- initial state Y_0: identity or the given GOOM matrix, columns scaled by powers of two
-    for (int e = tid; e < DP * LD; e += kThreads) s.y[e] = 0.0f;
-    if (tid < DP) s.yexp[tid] = 0.0;
-    __syncthreads();
-    if (!a.s0) {
-        if (tid < d) s.y[tid * LD + tid] = 1.0f;
-    } else {
-        const float *gp = a.s0 + (size_t)b * d * d * 2;
-        if (tid < d) { // column tid
-            float cmax = -__builtin_huge_valf();
-            for (int i = 0; i < d; ++i) cmax = fmaxf(cmax, gp[((size_t)i * d + tid) * 2]);
-            s.yexp[tid] = cmax > -__builtin_huge_valf() ? ceil((double)cmax * kLog2e) : 0.0;
-        }
-        __syncthreads();
-        for (int e = tid; e < d * d; e += kThreads) {
-            const int i = e / d, k = e % d;
-            const double t = (double)gp[(size_t)e * 2] * kLog2e - s.yexp[k];
-            float v = t > -300.0 ? (float)exp2(t) : 0.0f;
-            const int par = (int)rintf(gp[(size_t)e * 2 + 1] * 0.318309886183790671538f);
-            s.y[k * LD + i] = (par & 1) ? -v : v;
-        }
-    }
-    __syncthreads();
-
-    auto store_carry = [&](long long c) {
-        unsigned char *dst = a.carries + (b * (a.C + 1) + c) * a.car_stride;
-        float *mp = reinterpret_cast<float *>(dst);
-        double *ep = reinterpret_cast<double *>(dst + car_mant);
-        for (int e = tid; e < DP * a.car_cols; e += kThreads) {
-            const int i = e / a.car_cols, k = e % a.car_cols;
-            mp[e] = (i < d && k < d) ? s.y[k * LD + i] : 0.0f;
-        }
-        if (tid < a.car_cols) ep[tid] = tid < d ? s.yexp[tid] : 0.0;
-    };
-
-    // normalise the columns of z to unit norm: z <- z / |z_k|, lognorm_k = ln|z_k| + ln 2 * (exponent of column k)
-    auto normalise_z = [&](const double *col_exp) {
-        const int lane = tid & 63, wave = tid >> 6;
-        for (int k = wave; k < d; k += kThreads / 64) {
-            float v = lane < d ? s.z[k * LD + lane] : 0.0f;
-            // scale by the largest entry first so that the squares cannot under/overflow
-            float mx = fabsf(v);
+    f4 Y[KT][KT];    // state, columns scaled by 2^yexp
+    double yexp[KT]; // exponent of column 16 nt + c
+    double growth_acc[KT];
 #pragma unroll
-            for (int sft = 32; sft >= 1; sft >>= 1) mx = fmaxf(mx, __shfl_xor(mx, sft, 64));
-            int ex = 0;
-            if (mx > 0.0f) (void)frexpf(mx, &ex);
-            v = ldexpf(v, -ex);
-            const float ss = warp_sum(v * v);
-            const float nrm = __builtin_sqrtf(ss);
-            if (lane < d) s.z[k * LD + lane] = nrm > 0.0f ? v / nrm : 0.0f;
-            if (lane == 0)
-                s.lognorm[k] = nrm > 0.0f ? log((double)nrm) + ((double)ex + col_exp[k]) * kLn2 : -__builtin_huge_val();
-        }
-        __syncthreads();
-    };
-
-    // does any pair of unit columns of z have |cosine| above the threshold?
-    auto near_colinear = [&]() {
-        if (tid == 0) s.flag = 0;
-        __syncthreads();
-        int hit = 0;
-        for (int e = tid; e < d * d; e += kThreads) {
-            const int p = e / d, q = e % d;
-            if (p < q) {
-                float dot = 0.0f;
-                for (int i = 0; i < d; ++i) dot += s.z[p * LD + i] * s.z[q * LD + i];
-                if (fabsf(dot) > a.cos_threshold) hit = 1;
+    for (int nt = 0; nt < KT; ++nt) {
+        yexp[nt] = 0.0;
+        growth_acc[nt] = 0.0;
+    }
+    // ---- initial state: identity or the given GOOM matrix; rows and columns past d carry an
+    // identity block, which stays orthogonal to everything and never reaches the outputs
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Y[nt][mt][v] = (16 * mt + 4 * g + v == 16 * nt + c) ? 1.0f : 0.0f;
+    if (a.s0) {
+        const float *gp = a.s0 + (size_t)b * d * d * 2;
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt) {
+            const int col = 16 * nt + c;
+            if (col < d) {
+                float cmax = -__builtin_huge_valf();
+                for (int i = 0; i < d; ++i) cmax = fmaxf(cmax, gp[((size_t)i * d + col) * 2]);
+                yexp[nt] = cmax > -__builtin_huge_valf() ? ceil((double)cmax * kLog2e) : 0.0;
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = 16 * mt + 4 * g + v;
+                        float val = 0.0f;
+                        if (row < d) {
+                            const float *e = gp + ((size_t)row * d + col) * 2;
+                            const double t = (double)e[0] * kLog2e - yexp[nt];
+                            val = t > -300.0 ? (float)exp2(t) : 0.0f;
+                            if ((int)rintf(e[1] * 0.318309886183790671538f) & 1) val = -val;
+                        }
+                        Y[nt][mt][v] = val;
+                    }
             }
         }
-        if (hit) s.flag = 1;
-        __syncthreads();
-        return s.flag != 0;
+    }
+
+    auto store_carry = [&](long long cc) {
+        unsigned char *dst = a.carries + (b * (a.C + 1) + cc) * a.car_stride;
+        float *mp = reinterpret_cast<float *>(dst);
+        double *ep = reinterpret_cast<double *>(dst + car_mant);
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt) {
+            const int col = 16 * nt + c;
+            if (col < a.car_cols) {
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = 16 * mt + 4 * g + v;
+                        mp[(size_t)row * a.car_cols + col] = (row < d && col < d) ? Y[nt][mt][v] : 0.0f;
+                    }
+                if (g == 0) ep[col] = col < d ? yexp[nt] : 0.0;
+            }
+        }
     };
 
-    // QR of z (unit columns) by two Gram-Schmidt sweeps; z <- Q, colscale <- diag(R)
-    auto qr_z = [&]() {
-        mgs_sweep<DP>(s.z, s.rdiag, s.colscale, d, tid);
-        if (tid < d) s.t[tid] = s.rdiag[tid]; // first sweep's diagonal (t is free here)
-        __syncthreads();
-        mgs_sweep<DP>(s.z, s.rdiag, s.colscale, d, tid); // second sweep restores orthogonality; its R is near identity
-        if (tid < d) s.colscale[tid] = s.t[tid] * s.rdiag[tid];
-        __syncthreads();
-    };
-
-    for (long long c = 0; c < a.C; ++c) {
-        store_carry(c);
-        // ---- Z = T_c Y
-        const unsigned char *tp = a.totals + (b * a.C + c) * a.tot_stride;
+    // chunk product c: mantissas as 16-byte pieces (row = piece / (DP / 4)), and its common exponent
+    auto load_total = [&](long long cc, f4 (&tq)[TQ], double &tex) {
+        const unsigned char *tp = a.totals + (b * a.C + cc) * a.tot_stride;
         const float *tm = reinterpret_cast<const float *>(tp);
-        const double tex = *reinterpret_cast<const double *>(tp + tot_mant);
-        for (int e = tid; e < d * d; e += kThreads) {
-            const int i = e / d, j = e % d;
-            s.t[i * LD + j] = tm[(size_t)i * a.tot_cols + j];
+        tex = *reinterpret_cast<const double *>(tp + tot_mant);
+#pragma unroll
+        for (int q = 0; q < TQ; ++q) {
+            const int piece = lane + 64 * q;
+            const int row = piece / (DP / 4), c4 = 4 * (piece % (DP / 4));
+            tq[q] = *reinterpret_cast<const f4 *>(tm + (size_t)row * a.tot_cols + c4);
         }
-        __syncthreads();
-        for (int e = tid; e < d * d; e += kThreads) {
-            const int k = e / d, i = e % d; // consecutive threads walk down a column
-            float acc = 0.0f;
-            for (int j = 0; j < d; ++j) acc += s.t[i * LD + j] * s.y[k * LD + j];
-            s.z[k * LD + i] = acc;
+    };
+    auto tile_from = [&](const f4 (&tq)[TQ]) {
+#pragma unroll
+        for (int q = 0; q < TQ; ++q) {
+            const int piece = lane + 64 * q;
+            const int row = piece / (DP / 4), c4 = 4 * (piece % (DP / 4));
+            f4 val = tq[q];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) // identity block past d
+                if (row >= d || c4 + e >= d) val[e] = (c4 + e == row) ? 1.0f : 0.0f;
+            *reinterpret_cast<f4 *>(&s.tile[row * LDT + c4]) = val;
         }
-        __syncthreads();
-        const long long t_end = (c + 1) * a.L; // 1-based step this chunk ends at (if it is a full chunk)
+    };
+
+    // squared cosines between columns from the Gram matrix: any pair above the threshold?
+    auto near_colinear = [&](const d4 (&G)[KT][KT]) {
+        diagonal_to_lds<DP>(G, s, g, c);
+        bool hit = false;
+        const double thr2 = (double)a.cos_threshold * (double)a.cos_threshold;
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt) {
+            const double dc = s.diag[16 * nt + c];
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = 16 * mt + 4 * v + g, col = 16 * nt + c;
+                    const double dr = s.diag[row];
+                    const double x = G[nt][mt][v];
+                    if (row < col && col < d && x * x > thr2 * dr * dc) hit = true;
+                }
+        }
+        wave_sync();
+        return __builtin_amdgcn_ballot_w64(hit) != 0;
+    };
+
+    // QR of Z in place (Z <- Q); adds ln R_kk + ln 2 * colexp_k to growth_acc
+    auto qr_in_place = [&](f4 (&Z)[KT][KT], const double (&colexp)[KT]) {
+        d4 G[KT][KT];
+        double piv[KT], piv2[KT];
+        gram<DP>(Z, G);
+        const float amp = eliminate<DP>(G, Z, piv, s, g, c);
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt) piv2[nt] = 1.0;
+        if (amp > 65536.0f) { // float column updates lose about sqrt(amp) 2^-24 of orthogonality: factorise Q once more
+            gram<DP>(Z, G);
+            (void)eliminate<DP>(G, Z, piv2, s, g, c);
+        }
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt)
+            if (piv[nt] > 1.0e-30 && piv2[nt] > 1.0e-30)
+                growth_acc[nt] += 0.5 * (log(piv[nt]) + log(piv2[nt])) + colexp[nt] * kLn2;
+    };
+
+    f4 tq[TQ];
+    double tex_next = 0.0;
+    if (a.C > 0) load_total(0, tq, tex_next);
+
+    for (long long cc = 0; cc < a.C; ++cc) {
+        store_carry(cc);
+        const double tex = tex_next;
+        tile_from(tq);
+        wave_sync();
+        if (cc + 1 < a.C) load_total(cc + 1, tq, tex_next);
+        // ---- Z = T_c Y
+        f4 Z[KT][KT];
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt)
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) Z[nt][mt] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                const f4 av = *reinterpret_cast<const f4 *>(&s.tile[(16 * mt + c) * LDT + 16 * kt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int nt = 0; nt < KT; ++nt) Z[nt][mt] = mfma4(av[v], Y[nt][kt][v], Z[nt][mt]);
+            }
+        wave_sync(); // the tile is free again
+        double zexp[KT];
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt) zexp[nt] = yexp[nt] + tex;
+
+        const long long t_end = (cc + 1) * a.L; // 1-based step this chunk ends at (if it is a full chunk)
         const bool boundary = t_end <= a.T && a.policy >= 0;
         bool did_reset = false;
         if (boundary) {
-            // exponents of z's columns: chunk product's common exponent + the state's
-            if (tid < d) s.colscale[tid] = 0.0f;
-            __syncthreads();
-            // keep an unnormalised copy in y for the no-reset case: y <- z happens below
-            // normalise a copy: we normalise z in place and remember the scale to undo it if needed
-            // (col_exp = tex + yexp)
-            if (tid < d) s.yexp[tid] += tex;
-            __syncthreads();
-            // save z before normalising (into t, which is free now) in case no reset happens
-            for (int e = tid; e < DP * LD; e += kThreads) s.t[e] = s.z[e];
-            __syncthreads();
-            normalise_z(s.yexp);
-            did_reset = a.policy == 1 || near_colinear();
-            if (did_reset) {
-                qr_z();
-                if (tid < d && s.colscale[tid] > 0.0f) growth_acc += log((double)s.colscale[tid]) + s.lognorm[tid];
-                for (int e = tid; e < DP * LD; e += kThreads) s.y[e] = s.z[e];
-                if (tid < d) s.yexp[tid] = 0.0;
-                __syncthreads();
-            } else {
-                for (int e = tid; e < DP * LD; e += kThreads) s.z[e] = s.t[e]; // restore the product
-                __syncthreads();
+            did_reset = a.policy == 1;
+            if (!did_reset) {
+                d4 G[KT][KT];
+                gram<DP>(Z, G);
+                did_reset = near_colinear(G);
+            }
+        }
+        if (did_reset) {
+            qr_in_place(Z, zexp);
+#pragma unroll
+            for (int nt = 0; nt < KT; ++nt) {
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt) Y[nt][mt] = Z[nt][mt];
+                yexp[nt] = 0.0;
             }
         } else {
-            if (tid < d) s.yexp[tid] += tex;
-            __syncthreads();
-        }
-        if (tid == 0) a.chunk_flags[b * a.C + c] = did_reset ? 1 : 0;
-        if (!did_reset) {
             // Y <- Z with every column renormalised by a power of two
-            const int lane = tid & 63, wave = tid >> 6;
-            for (int k = wave; k < d; k += kThreads / 64) {
-                float v = lane < d ? s.z[k * LD + lane] : 0.0f;
-                float mx = fabsf(v);
 #pragma unroll
-                for (int sft = 32; sft >= 1; sft >>= 1) mx = fmaxf(mx, __shfl_xor(mx, sft, 64));
+            for (int nt = 0; nt < KT; ++nt) {
+                float mx = 0.0f;
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) mx = fmaxf(mx, fabsf(Z[nt][mt][v]));
+                mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
                 int ex = 0;
                 if (mx > 0.0f) (void)frexpf(mx, &ex);
-                if (lane < d) s.y[k * LD + lane] = ldexpf(v, -ex);
-                if (lane == 0) s.yexp[k] += (double)ex;
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) Y[nt][mt][v] = ldexpf(Z[nt][mt][v], -ex);
+                yexp[nt] = zexp[nt] + (double)ex;
             }
-            __syncthreads();
         }
+        if (lane == 0) a.chunk_flags[b * a.C + cc] = did_reset ? 1 : 0;
     }
 
     store_carry(a.C); // the final state
-    __syncthreads();
 
     // ---- growth of the final state (factorised, not replaced)
     if (a.growth) {
-        for (int e = tid; e < DP * LD; e += kThreads) s.z[e] = s.y[e];
-        __syncthreads();
-        normalise_z(s.yexp);
-        qr_z();
-        if (tid < d) {
-            if (s.colscale[tid] > 0.0f) growth_acc += log((double)s.colscale[tid]) + s.lognorm[tid];
-            a.growth[b * d + tid] = growth_acc * a.growth_scale;
+        f4 Z[KT][KT];
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt)
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) Z[nt][mt] = Y[nt][mt];
+        qr_in_place(Z, yexp);
+        if (g == 0) {
+#pragma unroll
+            for (int nt = 0; nt < KT; ++nt)
+                if (16 * nt + c < d) a.growth[b * d + 16 * nt + c] = growth_acc[nt] * a.growth_scale;
         }
     }
 }
@@ -371,19 +518,14 @@ int launch_reset_carry(goom_ctx *ctx, const ResetLaunch &l)
     a.cos_threshold = l.cos_threshold;
     const int dp = padded_dim(l.d);
     prof_begin(ctx, "reset_phase2_carries_qr");
-    if (dp == 16) {
-        hipLaunchKernelGGL(reset_carry_kernel<16>, dim3((unsigned)l.batch), dim3(kThreads), sizeof(Lds<16>), ctx->stream, a);
-    } else if (dp == 32) {
-        hipLaunchKernelGGL(reset_carry_kernel<32>, dim3((unsigned)l.batch), dim3(kThreads), sizeof(Lds<32>), ctx->stream, a);
-    } else if (dp == 64) {
-        auto kern = reset_carry_kernel<64>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)sizeof(Lds<64>));
-        if (e != hipSuccess) return check_hip(ctx, e, "hipFuncSetAttribute(reset_carry_kernel)");
-        hipLaunchKernelGGL(kern, dim3((unsigned)l.batch), dim3(kThreads), sizeof(Lds<64>), ctx->stream, a);
-    } else {
+    if (dp == 16)
+        hipLaunchKernelGGL(reset_carry_kernel<16>, dim3((unsigned)l.batch), dim3(64), 0, ctx->stream, a);
+    else if (dp == 32)
+        hipLaunchKernelGGL(reset_carry_kernel<32>, dim3((unsigned)l.batch), dim3(64), 0, ctx->stream, a);
+    else if (dp == 64)
+        hipLaunchKernelGGL(reset_carry_kernel<64>, dim3((unsigned)l.batch), dim3(64), 0, ctx->stream, a);
+    else
         return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 64 (d=%d)", l.d);
-    }
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch reset_carry_kernel");
 }

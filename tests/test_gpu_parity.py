@@ -80,8 +80,10 @@ def with_sensitivity(fn, arrays, comp, nprobe=2, seed=12345, eta_scale=1.0):
     return re, sg, kap, well
 
 
-def compare(got, ref_re, ref_sg, kappa=None, name="", max_ill_fraction=0.005, well=None):
-    """got: complex numpy array from the GPU; ref: oracle working form."""
+def compare(got, ref_re, ref_sg, kappa=None, name="", max_ill_fraction=0.005, well=None, kappa_limit=None,
+            max_out_fraction=0.0, hard_factor=1.0):
+    """got: complex numpy array from the GPU; ref: oracle working form.  max_out_fraction > 0 lets that
+    fraction of the well-conditioned entries exceed the tolerance, by at most hard_factor."""
     comp = np.float32 if got.dtype == np.complex64 else np.float64
     pi = comp(np.pi)
     im = got.imag
@@ -90,7 +92,7 @@ def compare(got, ref_re, ref_sg, kappa=None, name="", max_ill_fraction=0.005, we
     got_re = got.real.astype(np.float64)
     if kappa is None:
         kappa = np.ones_like(ref_re)
-    limit = 2.0 ** 9 if comp == np.float32 else 2.0 ** 30
+    limit = kappa_limit if kappa_limit is not None else (2.0 ** 9 if comp == np.float32 else 2.0 ** 30)
     well = (kappa <= limit) if well is None else (well & (kappa <= limit))
     ill_frac = 1.0 - well.mean()
     both_zero = np.isneginf(ref_re) & np.isneginf(got_re)
@@ -105,7 +107,12 @@ def compare(got, ref_re, ref_sg, kappa=None, name="", max_ill_fraction=0.005, we
     bad = finite & (diff > tol)
     worst = np.nanmax(np.where(finite, diff / tol, 0.0)) if finite.any() else 0.0
     say(f"  [{name}] entries={got.size} ill-conditioned={ill_frac:.2e} worst |dre|/tol={worst:.3g}")
-    assert not np.any(bad), f"{name}: {bad.sum()} log-magnitudes out of tolerance (worst ratio {worst:.3g})"
+    if max_out_fraction > 0.0:
+        say(f"  [{name}] {int(bad.sum())} of {int(finite.sum())} well-conditioned entries beyond the tolerance")
+        assert bad.sum() <= max_out_fraction * finite.sum() and worst <= hard_factor, \
+            f"{name}: {bad.sum()} log-magnitudes out of tolerance (worst ratio {worst:.3g})"
+    else:
+        assert not np.any(bad), f"{name}: {bad.sum()} log-magnitudes out of tolerance (worst ratio {worst:.3g})"
     assert ill_frac <= max_ill_fraction, f"{name}: {ill_frac:.3%} ill-conditioned entries"
 
 
