@@ -88,9 +88,9 @@ template <int DP> struct Wave {
     static constexpr int KT = DP / 16;
     static constexpr int LDT = DP + 4;
     float tile[DP * LDT]; // chunk product, row-major, rows padded against bank conflicts
-    double rrow[DP];      // row k of R, entry j at position j
-    double rperm[DP];     // the same with entry 16 mt + 4 v + g at position 16 mt + 4 g + v
-    float qcol[DP];       // column k of Q
+    double rrow[2][DP];   // row k of G at step k, entry j at position j (two sets, used alternately)
+    double rperm[2][DP];  // the same with entry 16 mt + 4 v + g at position 16 mt + 4 g + v
+    float qcol[2][DP];    // column k of Z at step k
     double diag[DP];      // diagonal of the Gram matrix
 };
 
@@ -128,8 +128,12 @@ template <int DP> __device__ void diagonal_to_lds(const d4 (&G)[DP / 16][DP / 16
     wave_sync();
 }
 
-// Cholesky elimination on (G, Z); piv[nt] receives the pivot of column 16 nt + c.  Returns the
-// largest ratio G_kk / pivot_k seen (1 for orthogonal columns).
+// Elimination on (G, Z) in its square-root-free form: step k subtracts (G_kj / p_k) times
+// row / column k from every later one, p_k = G_kk being the pivot; the columns of Z are scaled
+// by 1 / sqrt(p) once at the end.  The row and the column of step k go to LDS as they are, so
+// their round trip overlaps with the reciprocal of the pivot, which is the other half of the
+// dependent chain.  piv[nt] receives the pivot of column 16 nt + c.  Returns the largest ratio
+// G_kk / p_k seen (1 for orthogonal columns).
 template <int DP> __device__ float eliminate(d4 (&G)[DP / 16][DP / 16], f4 (&Z)[DP / 16][DP / 16], double (&piv)[DP / 16],
                                              Wave<DP> &s, int g, int c)
 {
@@ -142,57 +146,59 @@ template <int DP> __device__ float eliminate(d4 (&G)[DP / 16][DP / 16], f4 (&Z)[
     for (int k = 0; k < DP; ++k) {
         const int kb = k / 16, ck = k % 16;
         const int gk = ck % 4, vk = ck / 4; // row k of G: lanes with g == gk, register vk
-        const int gq = ck / 4;              // (rows of Z: row 16 mt + 4 g + v)
-        (void)gq;
-        const double pv = G[kb][kb][vk];
-        const int lo = __builtin_amdgcn_readlane((int)(__builtin_bit_cast(unsigned long long, pv) & 0xffffffffull), 16 * gk + ck);
-        const int hi = __builtin_amdgcn_readlane((int)(__builtin_bit_cast(unsigned long long, pv) >> 32), 16 * gk + ck);
-        const double pivot = __builtin_bit_cast(double, ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
-        const float scf = pivot > 1.0e-30 ? __builtin_amdgcn_rsqf((float)pivot) : 0.0f;
-        // one Newton step takes the float reciprocal square root to double accuracy where it matters
-        const double scd = pivot > 1.0e-30 ? (double)scf * (1.5 - 0.5 * pivot * (double)scf * (double)scf) : 0.0;
-        if (c == ck) piv[kb] = pivot;
-        // row k of R, entries right of the diagonal (zero elsewhere, so finished columns stay put)
+        const int buf = k & 1;              // two sets of LDS words, so a step need not wait for the previous one's readers
+        double *rrow = s.rrow[buf];
+        double *rperm = s.rperm[buf];
+        float *qcol = s.qcol[buf];
         if (g == gk) {
 #pragma unroll
             for (int nt = kb; nt < KT; ++nt) {
                 const int j = 16 * nt + c;
-                const double r = j > k ? G[nt][kb][vk] * scd : 0.0;
-                s.rrow[j] = r;
-                s.rperm[(j & ~15) | ((j & 3) << 2) | ((j >> 2) & 3)] = r;
+                const double r = j > k ? G[nt][kb][vk] : 0.0; // zero left of the diagonal: finished columns stay put
+                rrow[j] = r;
+                rperm[(j & ~15) | ((j & 3) << 2) | ((j >> 2) & 3)] = r;
             }
         }
-        // column k of Q
         if (c == ck) {
 #pragma unroll
-            for (int mt = 0; mt < KT; ++mt) {
-                Z[kb][mt] *= (float)scd;
-                *reinterpret_cast<f4 *>(&s.qcol[16 * mt + 4 * g]) = Z[kb][mt];
-            }
+            for (int mt = 0; mt < KT; ++mt) *reinterpret_cast<f4 *>(&qcol[16 * mt + 4 * g]) = Z[kb][mt];
         }
+        const double pv = G[kb][kb][vk];
+        const int lo = __builtin_amdgcn_readlane((int)(__builtin_bit_cast(unsigned long long, pv) & 0xffffffffull), 16 * gk + ck);
+        const int hi = __builtin_amdgcn_readlane((int)(__builtin_bit_cast(unsigned long long, pv) >> 32), 16 * gk + ck);
+        const double pivot = __builtin_bit_cast(double, ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
+        if (c == ck) piv[kb] = pivot;
+        // 1 / pivot: float reciprocal and one Newton step in double
+        const bool live = pivot > 1.0e-30;
+        const double r0 = (double)__builtin_amdgcn_rcpf((float)pivot);
+        const double inv = live ? r0 * (2.0 - pivot * r0) : 0.0;
         wave_sync();
-        double rj[KT];
+        double tj[KT];
 #pragma unroll
-        for (int nt = kb; nt < KT; ++nt) rj[nt] = s.rrow[16 * nt + c];
-#pragma unroll
-        for (int mt = 0; mt < KT; ++mt) {
-            const f4 qi = *reinterpret_cast<const f4 *>(&s.qcol[16 * mt + 4 * g]);
-#pragma unroll
-            for (int nt = kb; nt < KT; ++nt) Z[nt][mt] -= qi * (float)rj[nt];
-        }
+        for (int nt = kb; nt < KT; ++nt) tj[nt] = rrow[16 * nt + c] * inv;
 #pragma unroll
         for (int mt = kb; mt < KT; ++mt) {
             // this lane's rows of G are 16 mt + 4 v + g, v = 0..3: contiguous in the permuted copy
-            const d4 ri = *reinterpret_cast<const d4 *>(&s.rperm[16 * mt + 4 * g]);
+            const d4 ri = *reinterpret_cast<const d4 *>(&rperm[16 * mt + 4 * g]);
 #pragma unroll
-            for (int nt = kb; nt < KT; ++nt) G[nt][mt] -= ri * rj[nt];
+            for (int nt = kb; nt < KT; ++nt) G[nt][mt] -= ri * tj[nt];
         }
-        wave_sync();
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) {
+            const f4 zk = *reinterpret_cast<const f4 *>(&qcol[16 * mt + 4 * g]);
+#pragma unroll
+            for (int nt = kb; nt < KT; ++nt) Z[nt][mt] -= zk * (float)tj[nt];
+        }
     }
+    wave_sync();
     float worst = 1.0f;
 #pragma unroll
     for (int nt = 0; nt < KT; ++nt) {
-        const float ratio = piv[nt] > 1.0e-30 ? (float)(g0[nt] / piv[nt]) : 1.0f;
+        const bool live = piv[nt] > 1.0e-30;
+        const float sc = live ? __builtin_amdgcn_rsqf((float)piv[nt]) : 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) Z[nt][mt] *= sc;
+        const float ratio = live ? (float)g0[nt] * __builtin_amdgcn_rcpf((float)piv[nt]) : 1.0f;
         worst = fmaxf(worst, ratio);
     }
 #pragma unroll
@@ -215,11 +221,12 @@ template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(Reset
 
     f4 Y[KT][KT];    // state, columns scaled by 2^yexp
     double yexp[KT]; // exponent of column 16 nt + c
-    double growth_acc[KT];
+    double pprod[KT], pexp[KT]; // product of all pivots so far = pprod 2^pexp (column exponents counted twice: pivots are squares)
 #pragma unroll
     for (int nt = 0; nt < KT; ++nt) {
         yexp[nt] = 0.0;
-        growth_acc[nt] = 0.0;
+        pprod[nt] = 1.0;
+        pexp[nt] = 0.0;
     }
     // ---- initial state: identity or the given GOOM matrix; rows and columns past d carry an
     // identity block, which stays orthogonal to everything and never reaches the outputs
@@ -323,7 +330,9 @@ template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(Reset
         return __builtin_amdgcn_ballot_w64(hit) != 0;
     };
 
-    // QR of Z in place (Z <- Q); adds ln R_kk + ln 2 * colexp_k to growth_acc
+    // QR of Z in place (Z <- Q).  The growth it removes, ln R_kk + ln 2 * colexp_k per column, is
+    // kept as a running product of pivots (mantissa and binary exponent apart) plus a sum of
+    // exponents, so that no logarithm is taken inside the chain of chunks.
     auto qr_in_place = [&](f4 (&Z)[KT][KT], const double (&colexp)[KT]) {
         d4 G[KT][KT];
         double piv[KT], piv2[KT];
@@ -337,8 +346,11 @@ template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(Reset
         }
 #pragma unroll
         for (int nt = 0; nt < KT; ++nt)
-            if (piv[nt] > 1.0e-30 && piv2[nt] > 1.0e-30)
-                growth_acc[nt] += 0.5 * (log(piv[nt]) + log(piv2[nt])) + colexp[nt] * kLn2;
+            if (piv[nt] > 1.0e-30 && piv2[nt] > 1.0e-30) {
+                int e;
+                pprod[nt] = frexp(pprod[nt] * piv[nt] * piv2[nt], &e);
+                pexp[nt] += 2.0 * colexp[nt] + (double)e;
+            }
     };
 
     f4 tq[TQ];
@@ -427,7 +439,7 @@ template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(Reset
         if (g == 0) {
 #pragma unroll
             for (int nt = 0; nt < KT; ++nt)
-                if (16 * nt + c < d) a.growth[b * d + 16 * nt + c] = growth_acc[nt] * a.growth_scale;
+                if (16 * nt + c < d) a.growth[b * d + 16 * nt + c] = 0.5 * (log(pprod[nt]) + pexp[nt] * kLn2) * a.growth_scale;
         }
     }
 }
