@@ -700,3 +700,98 @@ ORACLE_API void oracle_reset_combine_real(double *a_prev, double *b_prev, double
     free(na);
     free(nb);
 }
+
+/* ------------------------------------------------------------------------- */
+/* Lyapunov spectrum from given input states (Section 4.2.1, groups (b)-(d))  */
+/* ------------------------------------------------------------------------- */
+
+/* For every step t = 1..T: the input state S_{t-1} (a GOOM matrix, working form: log-magnitudes
+ * and sign bytes; prev_re/prev_sg hold S_0 .. S_{T-1} back to back) is log-scaled to unit column
+ * norms and exponentiated, QR gives its orthonormal basis Q_{t-1} (group (b)); the real Jacobian
+ * J_t is applied to it (group (c)); QR of the result gives R_t, and log|diag R_t| is stored in
+ * steplog[t-1][:] (group (d)).  lambda[k] = mean_t steplog[t][k] / dt.  steplog may be NULL. */
+ORACLE_API void oracle_lyapunov_from_states(const double *prev_re, const uint8_t *prev_sg, const double *J,
+                                            double *steplog, double *lambda, long T, int d, double dt)
+{
+    size_t dd = (size_t)d * d;
+    long double *acc = (long double *)calloc((size_t)d, sizeof(long double));
+#pragma omp parallel
+    {
+        double *n = (double *)malloc(sizeof(double) * dd);
+        double *r = (double *)malloc(sizeof(double) * dd);
+        double *z = (double *)malloc(sizeof(double) * dd);
+        double *ln = (double *)malloc(sizeof(double) * (size_t)d);
+        long double *mine = (long double *)calloc((size_t)d, sizeof(long double));
+#pragma omp for schedule(static)
+        for (long t = 0; t < T; ++t) {
+            normalise_columns(prev_re + (size_t)t * dd, prev_sg + (size_t)t * dd, n, ln, d);
+            qr_householder(n, r, d); /* n <- Q_{t-1} */
+            const double *jt = J + (size_t)t * dd;
+            for (int i = 0; i < d; ++i)
+                for (int k = 0; k < d; ++k) {
+                    long double a = 0.0L;
+                    for (int j = 0; j < d; ++j) a += (long double)jt[(size_t)i * d + j] * n[(size_t)j * d + k];
+                    z[(size_t)i * d + k] = (double)a;
+                }
+            qr_householder(z, r, d);
+            for (int k = 0; k < d; ++k) {
+                double v = log(fabs(r[(size_t)k * d + k]));
+                if (steplog) steplog[(size_t)t * d + k] = v;
+                mine[k] += v;
+            }
+        }
+#pragma omp critical
+        for (int k = 0; k < d; ++k) acc[k] += mine[k];
+        free(n);
+        free(r);
+        free(z);
+        free(ln);
+        free(mine);
+    }
+    for (int k = 0; k < d; ++k) lambda[k] = (double)(acc[k] / ((long double)dt * (long double)T));
+    free(acc);
+}
+
+/* ------------------------------------------------------------------------- */
+/* largest Lyapunov exponent (Section 4.2.2)                                  */
+/* ------------------------------------------------------------------------- */
+
+/* The standard method (eqs. 14-15): s_t = J_t u_{t-1}, u_t = s_t / |s_t|,
+ * LLE = sum_t log(|s_t| / |u_{t-1}|) / (dt T).  Real Jacobians, double. */
+ORACLE_API double oracle_lle_standard(const double *J, const double *u0, long T, int d, double dt)
+{
+    double *u = (double *)malloc(sizeof(double) * (size_t)d);
+    double *s = (double *)malloc(sizeof(double) * (size_t)d);
+    long double acc = 0.0L;
+    memcpy(u, u0, sizeof(double) * (size_t)d);
+    for (long t = 0; t < T; ++t) {
+        const double *jt = J + (size_t)t * d * d;
+        long double nu = 0.0L, ns = 0.0L;
+        for (int i = 0; i < d; ++i) nu += (long double)u[i] * u[i];
+        for (int i = 0; i < d; ++i) {
+            long double a = 0.0L;
+            for (int j = 0; j < d; ++j) a += (long double)jt[(size_t)i * d + j] * u[j];
+            s[i] = (double)a;
+            ns += a * a;
+        }
+        acc += 0.5L * (logl(ns) - logl(nu));
+        long double inv = 1.0L / sqrtl(ns);
+        for (int i = 0; i < d; ++i) u[i] = (double)(s[i] * inv);
+    }
+    free(u);
+    free(s);
+    return (double)(acc / ((long double)dt * (long double)T));
+}
+
+/* The un-normalised form over GOOMs (eq. 17): LSE(2 * log-magnitudes of J_T ... J_1 u_0) / (2 dt T),
+ * given the final vector of that product in working form (from the scan oracle). */
+ORACLE_API double oracle_lle_from_final(const double *fre, long T, int d, double dt)
+{
+    double m = -INFINITY;
+    for (int i = 0; i < d; ++i)
+        if (2.0 * fre[i] > m) m = 2.0 * fre[i];
+    if (!(m > -INFINITY)) return -INFINITY;
+    long double acc = 0.0L;
+    for (int i = 0; i < d; ++i) acc += expl((long double)(2.0 * fre[i] - m));
+    return (double)(((long double)m + logl(acc)) / (2.0L * (long double)dt * (long double)T));
+}

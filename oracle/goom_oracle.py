@@ -283,3 +283,38 @@ def reset_combine_real(a_prev, b_prev, a_curr, b_curr, select_prev: bool, reset_
     lib().oracle_reset_combine_real(_p(ap), _p(bp), _p(ac), _p(bc), C.c_int(int(select_prev)),
                                     _p(rv), C.c_int(d))
     return ap, bp, ac, bc
+
+
+def lyapunov_from_states(prev_states, J: np.ndarray, dt: float):
+    """Groups (b)-(d) of Section 4.2.1: prev_states = (re, sg) of S_0 .. S_{T-1} (working form),
+    J the real Jacobians [T, d, d].  Returns (lambda [d], per-step log|diag R| [T, d])."""
+    pre, psg = _as_working(prev_states)
+    J = _c(J, np.float64)
+    T, d, _ = J.shape
+    assert pre.shape == (T, d, d)
+    steplog = np.empty((T, d), dtype=np.float64)
+    lam = np.empty((d,), dtype=np.float64)
+    lib().oracle_lyapunov_from_states(_p(pre), _p(psg), _p(J), _p(steplog), _p(lam), C.c_long(T), C.c_int(d),
+                                      C.c_double(dt))
+    return lam, steplog
+
+
+def lle_standard(J: np.ndarray, u0: np.ndarray, dt: float) -> float:
+    """Largest Lyapunov exponent by the normalised vector iteration (Section 4.2.2, eqs. 14-15)."""
+    J = _c(J, np.float64)
+    u0 = _c(u0, np.float64)
+    T, d, _ = J.shape
+    f = lib().oracle_lle_standard
+    f.restype = C.c_double
+    return float(f(_p(J), _p(u0), C.c_long(T), C.c_int(d), C.c_double(dt)))
+
+
+def lle_goom(jac, u0, dt: float, scaled: bool = False) -> float:
+    """Largest Lyapunov exponent as LSE(2 * scan(J_T ... J_1 u_0)) / (2 dt T) (Section 4.2.2, eq. 17):
+    jac [T, d, d] and u0 [d] are GOOMs; the product is walked by the scan oracle."""
+    T, d, _ = np.asarray(jac).shape if not isinstance(jac, tuple) else jac[0].shape
+    init = np.asarray(u0).reshape(d, 1)
+    fre, _ = ScanStream(d, m=1, init=init, scaled=scaled).advance(jac, sample_t=[T - 1])
+    f = lib().oracle_lle_from_final
+    f.restype = C.c_double
+    return float(f(_p(_c(fre.reshape(d), np.float64)), C.c_long(T), C.c_int(d), C.c_double(dt)))

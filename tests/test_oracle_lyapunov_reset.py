@@ -134,3 +134,71 @@ def test_reset_states_are_orthonormal_after_reset(oracle):
     for t in np.nonzero(flag)[0]:
         q = real_of(re[t], sg[t])
         assert np.allclose(q.T @ q, np.eye(6), atol=1e-10)
+
+
+# ------------------------------------------------- largest exponent (Section 4.2.2)
+
+def test_lle_standard_is_first_exponent_of_qr_method(oracle):
+    # with u_0 = e_1 the normalised vector iteration IS the first column of the QR iteration
+    J, _ = si.lorenz96_jacobians(si.BASE_SEED + 9, 3000, d=8, burn_in=500)
+    e1 = np.zeros(8)
+    e1[0] = 1.0
+    lle = oracle.lle_standard(J, e1, 0.01)
+    assert abs(lle - oracle.lyapunov_qr(J, 0.01)[0]) < 1e-10
+    # closed form for products of Gaussian matrices (d = 8): (ln 2 + psi(4)) / 2, any unit start
+    T, d = 20000, 8
+    G = si.normal_chain(si.BASE_SEED + 10, T, d)
+    u0 = np.ones(d) / math.sqrt(d)
+    want = 0.5 * (math.log(2.0) + digamma(d / 2))
+    sigma = math.sqrt(0.25 * 0.2838 / T)  # var of log chi^2_8 / 4 per step, trigamma(4) = 0.2838
+    assert abs(oracle.lle_standard(G, u0, 1.0) - want) < 5 * sigma + 1e-3
+
+
+def test_lle_over_gooms_equals_standard_method(oracle):
+    # without normalisation the sum telescopes to log|J_T ... J_1 u_0| / (dt T): LSE(2 x') / 2 over GOOMs
+    T, d = 600, 8
+    J, _ = si.lorenz96_jacobians(si.BASE_SEED + 11, T, d=d, burn_in=500)
+    u0 = si.normal_f32(si.BASE_SEED + 11, 3, d).astype(np.float64)
+    u0 /= np.linalg.norm(u0)
+    want = oracle.lle_standard(J, u0, 0.01)
+    Jz, uz = oracle.to_goom(J.astype(np.float64)), oracle.to_goom(u0)
+    assert abs(oracle.lle_goom(Jz, uz, 0.01) - want) < 1e-9
+    assert abs(oracle.lle_goom(Jz, uz, 0.01, scaled=True) - want) < 1e-9
+    # far past double range: 3000 Gaussian 16 x 16 factors (log-norm about 4000)
+    T, d = 3000, 16
+    G = si.normal_chain(si.BASE_SEED + 12, T, d)
+    u0 = np.ones(d) / math.sqrt(d)
+    got = oracle.lle_goom(oracle.to_goom(G.astype(np.float64)), oracle.to_goom(u0), 1.0, scaled=True)
+    assert abs(got - oracle.lle_standard(G, u0, 1.0)) < 1e-9 and got * T > 3500
+
+
+# ------------------------------------- spectrum from input states (Section 4.2.1 (b)-(d))
+
+def _input_states(oracle, Jz, L, policy):
+    """S_0 = I, S_1 .. S_{T-1} from the selectively reset recurrence, in working form."""
+    T, d, _ = Jz.shape
+    re, sg, _, _ = oracle.reset_scan(Jz, None, check_every=L, policy=policy)
+    eye_re = np.where(np.eye(d) > 0, 0.0, -np.inf)
+    pre = np.concatenate([eye_re[None], re[:-1]])
+    psg = np.concatenate([np.zeros((1, d, d), np.uint8), sg[:-1]])
+    return pre, psg
+
+
+def test_spectrum_from_states_equals_sequential_qr(oracle):
+    # any basis of the same nested subspaces gives the same Q_{t-1}, hence the same R_t: the groups
+    # (b)-(d) on selectively reset states reproduce the step-by-step method
+    T, d = 300, 8
+    J, _ = si.lorenz96_jacobians(si.BASE_SEED + 13, T, d=d, burn_in=500)
+    Jz = oracle.to_goom(J.astype(np.float64))
+    want = oracle.lyapunov_qr(J, 0.01)
+    for L, policy in ((5, 1), (1, 1), (7, 0), (0, -1)):
+        lam, steplog = oracle.lyapunov_from_states(_input_states(oracle, Jz, L, policy), J, 0.01)
+        tol = 1e-8 if policy >= 0 else 1e-4  # never resetting: the states nearly collapse even in double
+        assert np.abs(lam - want).max() < tol, (L, policy, np.abs(lam - want).max())
+        # per step, sum_k log R_kk = log|det J_t|, whatever the basis
+        dets = np.array([np.linalg.slogdet(j.astype(np.float64))[1] for j in J])
+        assert np.abs(steplog.sum(axis=1) - dets).max() < (1e-9 if policy >= 0 else 1e-5)
+    # using the OUTPUT state of each step instead of its input state is wrong, and shows
+    re, sg, _, _ = oracle.reset_scan(Jz, None, check_every=5, policy=1)
+    bad, _ = oracle.lyapunov_from_states((re, sg), J, 0.01)
+    assert np.abs(bad - want).max() > 1e-3
