@@ -271,6 +271,17 @@ def other_workloads(g, torch, dev):
     res["lyapunov_lorenz96_d32_T131072"] = {
         "ms": round(sec * 1e3, 3), "jacobians_per_s": round(T / sec, 1), "lambda_1": round(float(lam[0]), 4),
         "kernels_ms": kernel_times(g, lambda: g.lyapunov_spectrum(Jz, 0.01))}
+    sec = timed(torch, lambda: g.lyapunov_spectrum(Jz, 0.01, chunk_len=64))
+    res["lyapunov_lorenz96_d32_T131072_chunk64"] = {"ms": round(sec * 1e3, 3), "jacobians_per_s": round(T / sec, 1)}
+    sec = timed(torch, lambda: g.lyapunov_spectrum_per_step(Jz, 0.01))
+    res["lyapunov_per_step_qr_d32_T131072"] = {
+        "ms": round(sec * 1e3, 3), "jacobians_per_s": round(T / sec, 1),
+        "kernels_ms": kernel_times(g, lambda: g.lyapunov_spectrum_per_step(Jz, 0.01))}
+    sec = timed(torch, lambda: g.largest_lyapunov(Jz, 0.01))
+    res["largest_lyapunov_d32_T131072"] = {
+        "ms": round(sec * 1e3, 3), "jacobians_per_s": round(T / sec, 1),
+        "lle": round(float(g.largest_lyapunov(Jz, 0.01).cpu()), 4),
+        "kernels_ms": kernel_times(g, lambda: g.largest_lyapunov(Jz, 0.01))}
     sec = timed(torch, lambda: g.scan_reset(Jz))
     res["reset_scan_all_states_d32_T131072"] = {
         "ms": round(sec * 1e3, 3), "jacobians_per_s": round(T / sec, 1),

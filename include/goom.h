@@ -198,6 +198,32 @@ int goom_lyapunov_spectrum(goom_ctx *ctx, const void *J, const void *S0, void *s
                            double *lambda, int64_t T, int d, double dt, int64_t batch, int dtype,
                            const goom_reset_opts *opts, void *workspace, size_t workspace_bytes);
 
+/* Lyapunov spectrum by the paper's four groups of parallel computations (Section 4.2.1
+ * (a)-(d)): (a) the selectively reset scan above gives the input states S_0 .. S_{T-1};
+ * (b) each is log-scaled and factorised, S_{t-1} -> Q_{t-1}; (c) S*_t = J_t Q_{t-1};
+ * (d) S*_t -> R_t, and lambda[b, k] = mean over t of log R_t,kk / dt.  Every step of (b)-(d)
+ * is independent of the others.  states: NULL or [batch, T, d, d] (as in goom_scan_reset);
+ * step_logs: NULL or [batch, T, d] doubles receiving log R_t,kk; lambda: [batch, d] doubles.
+ * workspace: goom_lyapunov_spectrum_per_step_workspace_bytes(..., states != NULL,
+ * step_logs != NULL) bytes. */
+int goom_lyapunov_spectrum_per_step(goom_ctx *ctx, const void *J, const void *S0, void *states,
+                                    double *step_logs, double *lambda, int64_t T, int d, double dt,
+                                    int64_t batch, int dtype, const goom_reset_opts *opts,
+                                    void *workspace, size_t workspace_bytes);
+size_t goom_lyapunov_spectrum_per_step_workspace_bytes(int64_t T, int d, int64_t batch, int dtype,
+                                                       const goom_reset_opts *opts,
+                                                       int caller_has_states, int caller_has_step_logs);
+
+/* Largest Lyapunov exponent (paper Section 4.2.2): lle[b] = LSE(2 v') / (2 dt T) with
+ * v' the GOOM vector J[b, T-1] ... J[b, 0] u0[b], computed as a reduction over the chain.
+ * J: [batch, T, d, d]; u0: NULL (all entries 1 / sqrt(d)) or [batch, d] GOOMs; lle: [batch]
+ * doubles.  workspace: goom_largest_lyapunov_workspace_bytes(...) bytes. */
+int goom_largest_lyapunov(goom_ctx *ctx, const void *J, const void *u0, double *lle, int64_t T,
+                          int d, double dt, int64_t batch, int dtype, const goom_scan_opts *opts,
+                          void *workspace, size_t workspace_bytes);
+size_t goom_largest_lyapunov_workspace_bytes(int64_t T, int d, int64_t batch, int dtype,
+                                             const goom_scan_opts *opts);
+
 /* ---- linear recurrence with bias (paper Section 4.3, eqs. 18 and 20) ---------------- */
 
 /* h[b, t] = A[b, t] h[b, t-1] + bias[b, t], h[b, -1] = h0[b] (NULL = zero vector), over

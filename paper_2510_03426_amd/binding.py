@@ -24,6 +24,8 @@ EXPORTS = [
     "goom_status_name", "goom_profile_enable", "goom_profile_count", "goom_profile_get", "goom_to_goom", "goom_from_goom", "goom_lmme", "goom_lmme_workspace_bytes",
     "goom_scan", "goom_scan_workspace_bytes", "goom_reduce", "goom_reduce_workspace_bytes",
     "goom_scan_reset", "goom_scan_reset_workspace_bytes", "goom_lyapunov_spectrum",
+    "goom_lyapunov_spectrum_per_step", "goom_lyapunov_spectrum_per_step_workspace_bytes",
+    "goom_largest_lyapunov", "goom_largest_lyapunov_workspace_bytes",
     "goom_affine_scan", "goom_affine_scan_workspace_bytes",
 ]
 
@@ -84,6 +86,12 @@ def load_library():
     lib.goom_scan_reset_workspace_bytes.argtypes = [i64, i32, i64, i32, pr]
     lib.goom_scan_reset_workspace_bytes.restype = sz
     lib.goom_lyapunov_spectrum.argtypes = [vp, vp, vp, vp, vp, i64, i32, C.c_double, i64, i32, pr, vp, sz]
+    lib.goom_lyapunov_spectrum_per_step.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, C.c_double, i64, i32, pr, vp, sz]
+    lib.goom_lyapunov_spectrum_per_step_workspace_bytes.argtypes = [i64, i32, i64, i32, pr, i32, i32]
+    lib.goom_lyapunov_spectrum_per_step_workspace_bytes.restype = sz
+    lib.goom_largest_lyapunov.argtypes = [vp, vp, vp, vp, i64, i32, C.c_double, i64, i32, po, vp, sz]
+    lib.goom_largest_lyapunov_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
+    lib.goom_largest_lyapunov_workspace_bytes.restype = sz
     lib.goom_affine_scan.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
     lib.goom_affine_scan_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_affine_scan_workspace_bytes.restype = sz
@@ -299,3 +307,38 @@ class Goom:
         self._check(self.lib.goom_lyapunov_spectrum(self._ctx, _ptr(jac), _ptr(s0), None, _ptr(lam), T, d, dt, batch,
                                                     code, C.byref(opts), _ptr(ws), wsn))
         return lam
+
+    def lyapunov_spectrum_per_step(self, jac, dt: float, s0=None, chunk_len: int = 0, policy: int = RESET_ALWAYS,
+                                   cos_threshold: float = 0.99, want_step_logs: bool = False):
+        """Spectrum by the four groups of parallel computations (two QRs per step)."""
+        torch = self.torch
+        code = _dtype_code(jac)
+        T, d, _ = jac.shape[-3:]
+        lead = jac.shape[:-3]
+        batch = 1
+        for s in lead:
+            batch *= s
+        opts = ResetOpts(chunk_len, policy, cos_threshold)
+        lam = torch.zeros(lead + (d,), dtype=torch.float64, device=jac.device)
+        logs = torch.zeros(lead + (T, d), dtype=torch.float64, device=jac.device) if want_step_logs else None
+        ws, wsn = self.workspace(self.lib.goom_lyapunov_spectrum_per_step_workspace_bytes(
+            T, d, batch, code, C.byref(opts), 0, 1 if want_step_logs else 0))
+        self._check(self.lib.goom_lyapunov_spectrum_per_step(self._ctx, _ptr(jac), _ptr(s0), None, _ptr(logs), _ptr(lam),
+                                                             T, d, dt, batch, code, C.byref(opts), _ptr(ws), wsn))
+        return (lam, logs) if want_step_logs else lam
+
+    def largest_lyapunov(self, jac, dt: float, u0=None, chunk_len: int = 0):
+        """Largest exponent as LSE(2 v') / (2 dt T), v' = J_T ... J_1 u_0 over GOOMs."""
+        torch = self.torch
+        code = _dtype_code(jac)
+        T, d, _ = jac.shape[-3:]
+        lead = jac.shape[:-3]
+        batch = 1
+        for s in lead:
+            batch *= s
+        opts = ScanOpts(chunk_len, 0)
+        lle = torch.zeros(lead, dtype=torch.float64, device=jac.device)
+        ws, wsn = self.workspace(self.lib.goom_largest_lyapunov_workspace_bytes(T, d, batch, code, C.byref(opts)))
+        self._check(self.lib.goom_largest_lyapunov(self._ctx, _ptr(jac), _ptr(u0), _ptr(lle), T, d, dt, batch, code,
+                                                   C.byref(opts), _ptr(ws), wsn))
+        return lle

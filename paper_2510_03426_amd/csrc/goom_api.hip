@@ -757,4 +757,78 @@ int goom_lyapunov_spectrum(goom_ctx *ctx, const void *J, const void *S0, void *s
                      workspace_bytes);
 }
 
+size_t goom_lyapunov_spectrum_per_step_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts,
+                                                       int caller_has_states, int caller_has_step_logs)
+{
+    if (T <= 0 || d <= 0 || batch <= 0 || d > 64 || dtype != GOOM_C64) return 0;
+    const ResetPlan p = plan_reset(T, d, batch, dtype, opts);
+    size_t n = p.total() + lyap_steps_partial_bytes(batch, d);
+    if (!caller_has_states) n += align_up((size_t)batch * T * d * d * 8, 256);
+    if (!caller_has_step_logs) n += align_up((size_t)batch * T * d * sizeof(double), 256);
+    return n;
+}
+
+int goom_lyapunov_spectrum_per_step(goom_ctx *ctx, const void *J, const void *S0, void *states, double *step_logs,
+                                    double *lambda, int64_t T, int d, double dt, int64_t batch, int dtype,
+                                    const goom_reset_opts *opts, void *workspace, size_t workspace_bytes)
+{
+    if (int s = check_common(ctx, dtype)) return s;
+    if (!lambda || !J) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    if (!(dt > 0.0)) return fail(ctx, GOOM_EINVAL, "dt must be positive");
+    if (T <= 0 || batch <= 0 || d <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive (T=%lld d=%d batch=%lld)", (long long)T, d, (long long)batch);
+    if (dtype != GOOM_C64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan is built for GOOM_C64 only");
+    if (d > 64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 64 (d=%d)", d);
+    if (step_logs && !aligned(step_logs, 8)) return fail(ctx, GOOM_EINVAL, "step_logs must be 8-byte aligned");
+    const size_t need = goom_lyapunov_spectrum_per_step_workspace_bytes(T, d, batch, dtype, opts, states != nullptr, step_logs != nullptr);
+    if (int s = check_workspace(ctx, workspace, workspace_bytes, need)) return s;
+    const ResetPlan p = plan_reset(T, d, batch, dtype, opts);
+    unsigned char *w = static_cast<unsigned char *>(workspace) + p.total();
+    double *partial = reinterpret_cast<double *>(w);
+    w += lyap_steps_partial_bytes(batch, d);
+    if (!states) {
+        states = w;
+        w += align_up((size_t)batch * T * d * d * 8, 256);
+    }
+    if (!step_logs) step_logs = reinterpret_cast<double *>(w);
+    // group (a): all states, selectively reset
+    if (int s = run_reset(ctx, J, S0, states, nullptr, nullptr, 1.0, T, d, batch, dtype, opts, workspace, p.total())) return s;
+    // groups (b)-(d)
+    return launch_lyap_steps(ctx, J, S0, states, step_logs, partial, lambda, T, d, batch, 1.0 / (dt * (double)T));
+}
+
+size_t goom_largest_lyapunov_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts)
+{
+    if (T <= 0 || d <= 0 || batch <= 0 || d > GOOM_MAX_DIM) return 0;
+    if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
+    const ScanPlan p = plan_scan(T, d, d, 1, batch, dtype, opts ? opts->chunk_len : 0, true);
+    const size_t vec = align_up((size_t)batch * d * 2 * comp_bytes(dtype), 256);
+    return align_up(p.total(), 256) + 2 * vec;
+}
+
+int goom_largest_lyapunov(goom_ctx *ctx, const void *J, const void *u0, double *lle, int64_t T, int d, double dt,
+                          int64_t batch, int dtype, const goom_scan_opts *opts, void *workspace, size_t workspace_bytes)
+{
+    if (int s = check_common(ctx, dtype)) return s;
+    if (!lle || !J) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    if (!(dt > 0.0)) return fail(ctx, GOOM_EINVAL, "dt must be positive");
+    if (T <= 0 || batch <= 0 || d <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive (T=%lld d=%d batch=%lld)", (long long)T, d, (long long)batch);
+    if (d > GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "d must be <= %d", GOOM_MAX_DIM);
+    if (!aligned(lle, 8)) return fail(ctx, GOOM_EINVAL, "lle must be 8-byte aligned");
+    const size_t need = goom_largest_lyapunov_workspace_bytes(T, d, batch, dtype, opts);
+    if (int s = check_workspace(ctx, workspace, workspace_bytes, need)) return s;
+    const ScanPlan p = plan_scan(T, d, d, 1, batch, dtype, opts ? opts->chunk_len : 0, true);
+    const size_t scan_ws = align_up(p.total(), 256);
+    const size_t vec = align_up((size_t)batch * d * 2 * comp_bytes(dtype), 256);
+    unsigned char *w = static_cast<unsigned char *>(workspace);
+    void *final_vec = w + scan_ws;
+    void *u_default = w + scan_ws + vec;
+    if (!u0) {
+        if (int s = need_ctx(ctx)) return s;
+        if (int s = launch_uniform_u0(ctx, u_default, batch, d, dtype)) return s;
+        u0 = u_default;
+    }
+    if (int s = run_scan(ctx, J, u0, final_vec, T, d, 1, batch, dtype, opts, workspace, scan_ws, true)) return s;
+    return launch_lle_epilogue(ctx, final_vec, lle, batch, d, dtype, 1.0 / (2.0 * dt * (double)T));
+}
+
 } // extern "C"

@@ -107,6 +107,11 @@ struct ResetLaunch {
 };
 int launch_reset_carry(goom_ctx *ctx, const ResetLaunch &l);
 int launch_reset_post(goom_ctx *ctx, const ResetLaunch &l);
+int launch_lyap_steps(goom_ctx *ctx, const void *J, const void *S0, const void *states, double *steplog, double *partial,
+                      double *lambda, long long T, int d, long long batch, double scale);
+size_t lyap_steps_partial_bytes(long long batch, int d);
+int launch_lle_epilogue(goom_ctx *ctx, const void *v, double *lle, long long batch, int d, int dtype, double scale);
+int launch_uniform_u0(goom_ctx *ctx, void *u, long long batch, int d, int dtype);
 
 int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int n, int d, int m, int dtype);
 

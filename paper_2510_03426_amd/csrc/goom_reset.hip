@@ -444,6 +444,212 @@ template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(Reset
     }
 }
 
+// Spectrum from the input states (paper Section 4.2.1, groups (b)-(d)): one wave per step t.
+// The input state S_{t-1} is log-scaled column by column and exponentiated, its QR gives the
+// orthonormal basis Q_{t-1}; J_t (scaled by one power of two for the whole matrix) is applied to
+// it on the matrix unit, and the QR of the result gives R_t; log R_kk goes to steplog[b][t][k].
+// Every step is independent of the others.
+struct StepArgs {
+    const float *J;      // [batch][T][d][d] GOOMs
+    const float *S0;     // NULL (identity) or [batch][d][d] GOOMs
+    const float *states; // [batch][T][d][d] GOOMs: entry t holds the state after step t + 1
+    double *steplog;     // [batch][T][d]
+    long long T;
+    int d;
+};
+
+template <int DP> __global__ __launch_bounds__(64) void lyap_step_kernel(StepArgs a)
+{
+    constexpr int KT = DP / 16;
+    constexpr int LDT = DP + 4;
+    constexpr int TQ = DP * DP / 4 / 64;
+    __shared__ __align__(16) Wave<DP> s;
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, c = lane & 15;
+    const int d = a.d;
+    const long long b = blockIdx.x / a.T, t = blockIdx.x % a.T;
+    const float kLog2eF = 1.44269504088896340736f;
+
+    // ---- input state, columns scaled to largest entry 1 (identity block past d)
+    const float *src = t == 0 ? (a.S0 ? a.S0 + (size_t)b * d * d * 2 : nullptr) : a.states + (size_t)(b * a.T + t - 1) * d * d * 2;
+    f4 Q[KT][KT];
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) {
+        const int col = 16 * nt + c;
+        float re[KT][4], im[KT][4];
+        float cmax = -__builtin_huge_valf();
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * mt + 4 * g + v;
+                float r = row == col ? 0.0f : -__builtin_huge_valf(), i = 0.0f;
+                if (src && row < d && col < d) {
+                    const float2 e = *reinterpret_cast<const float2 *>(src + ((size_t)row * d + col) * 2);
+                    r = e.x;
+                    i = e.y;
+                }
+                re[mt][v] = r;
+                im[mt][v] = i;
+                cmax = fmaxf(cmax, r);
+            }
+        cmax = fmaxf(cmax, __shfl_xor(cmax, 16, 64));
+        cmax = fmaxf(cmax, __shfl_xor(cmax, 32, 64));
+        const bool zero_col = !(cmax > -__builtin_huge_valf());
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float x = zero_col ? 0.0f : __builtin_amdgcn_exp2f((re[mt][v] - cmax) * kLog2eF);
+                if ((int)rintf(im[mt][v] * 0.318309886183790671538f) & 1) x = -x;
+                Q[nt][mt][v] = x;
+            }
+    }
+    {
+        d4 G[KT][KT];
+        double piv[KT];
+        gram<DP>(Q, G);
+        const float amp = eliminate<DP>(G, Q, piv, s, g, c);
+        if (amp > 65536.0f) {
+            gram<DP>(Q, G);
+            (void)eliminate<DP>(G, Q, piv, s, g, c);
+        }
+    }
+
+    // ---- J_t as reals scaled by 2^-sh, sh from the largest entry; identity block past d
+    const float *jp = a.J + (size_t)(b * a.T + t) * d * d * 2;
+    float jre[TQ][4], jim[TQ][4];
+    float jmax = -__builtin_huge_valf();
+#pragma unroll
+    for (int q = 0; q < TQ; ++q) {
+        const int piece = lane + 64 * q;
+        const int row = piece / (DP / 4), c4 = 4 * (piece % (DP / 4));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float r = -__builtin_huge_valf(), i = 0.0f;
+            if (row < d && c4 + e < d) {
+                const float2 v = *reinterpret_cast<const float2 *>(jp + ((size_t)row * d + c4 + e) * 2);
+                r = v.x;
+                i = v.y;
+            }
+            jre[q][e] = r;
+            jim[q][e] = i;
+            jmax = fmaxf(jmax, r);
+        }
+    }
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) jmax = fmaxf(jmax, __shfl_xor(jmax, sft, 64));
+    const float sh = jmax > -__builtin_huge_valf() ? ceilf(jmax * kLog2eF) : 0.0f;
+#pragma unroll
+    for (int q = 0; q < TQ; ++q) {
+        const int piece = lane + 64 * q;
+        const int row = piece / (DP / 4), c4 = 4 * (piece % (DP / 4));
+        f4 val;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float x = __builtin_amdgcn_exp2f(__builtin_fmaf(jre[q][e], kLog2eF, -sh));
+            if ((int)rintf(jim[q][e] * 0.318309886183790671538f) & 1) x = -x;
+            if (row >= d || c4 + e >= d) x = (c4 + e == row) ? 1.0f : 0.0f;
+            val[e] = x;
+        }
+        *reinterpret_cast<f4 *>(&s.tile[row * LDT + c4]) = val;
+    }
+    wave_sync();
+    f4 Z[KT][KT];
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) Z[nt][mt] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) {
+            const f4 av = *reinterpret_cast<const f4 *>(&s.tile[(16 * mt + c) * LDT + 16 * kt + 4 * g]);
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int nt = 0; nt < KT; ++nt) Z[nt][mt] = mfma4(av[v], Q[nt][kt][v], Z[nt][mt]);
+        }
+    wave_sync();
+    d4 G[KT][KT];
+    double piv[KT], piv2[KT];
+    gram<DP>(Z, G);
+    const float amp = eliminate<DP>(G, Z, piv, s, g, c);
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) piv2[nt] = 1.0;
+    if (amp > 65536.0f) {
+        gram<DP>(Z, G);
+        (void)eliminate<DP>(G, Z, piv2, s, g, c);
+    }
+    if (g == 0) {
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt) {
+            const int col = 16 * nt + c;
+            if (col < d) {
+                const double p = piv[nt] * piv2[nt];
+                a.steplog[(size_t)(b * a.T + t) * d + col] = p > 1.0e-60 ? 0.5 * log(p) + (double)sh * kLn2 : -__builtin_huge_val();
+            }
+        }
+    }
+}
+
+// lambda[b][k] = scale * sum_t steplog[b][t][k], summed in a fixed order: kSlices slices of the
+// steps per batch item, partial sums in the workspace, then one block adds the slices.
+constexpr int kSlices = 64;
+
+__global__ __launch_bounds__(256) void steplog_partial_kernel(const double *steplog, double *partial, long long T, int d)
+{
+    __shared__ double red[256];
+    const long long b = blockIdx.x / kSlices;
+    const int slice = blockIdx.x % kSlices;
+    const int k = threadIdx.x & 63, r = threadIdx.x >> 6; // 4 groups of 64 threads; thread k < d owns exponent k
+    const long long per = (T + kSlices - 1) / kSlices;
+    const long long lo = slice * per, hi = lo + per < T ? lo + per : T;
+    double acc = 0.0;
+    if (k < d)
+        for (long long t = lo + r; t < hi; t += 4) acc += steplog[(size_t)(b * T + t) * d + k];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (r == 0 && k < d) partial[(size_t)(b * kSlices + slice) * d + k] = ((red[k] + red[64 + k]) + red[128 + k]) + red[192 + k];
+}
+
+__global__ void steplog_final_kernel(const double *partial, double *lambda, int d, double scale)
+{
+    const long long b = blockIdx.x;
+    const int k = threadIdx.x;
+    if (k >= d) return;
+    double acc = 0.0;
+    for (int sl = 0; sl < kSlices; ++sl) acc += partial[(size_t)(b * kSlices + sl) * d + k];
+    lambda[b * d + k] = acc * scale;
+}
+
+// Largest exponent from the final vector v = J_T ... J_1 u_0 (paper Section 4.2.2):
+// LSE(2 Re v') / (2 dt T); one thread per batch item.
+template <typename R> __global__ void lle_epilogue_kernel(const R *v, double *lle, long long batch, int d, double scale)
+{
+    const long long b = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= batch) return;
+    const R *p = v + (size_t)b * d * 2;
+    double m = -__builtin_huge_val();
+    for (int i = 0; i < d; ++i) m = fmax(m, 2.0 * (double)p[2 * i]);
+    if (!(m > -__builtin_huge_val())) {
+        lle[b] = -__builtin_huge_val();
+        return;
+    }
+    double acc = 0.0;
+    for (int i = 0; i < d; ++i) acc += exp(2.0 * (double)p[2 * i] - m);
+    lle[b] = (m + log(acc)) * scale;
+}
+
+// u_0 = (1, ..., 1) / sqrt(d) as GOOMs
+template <typename R> __global__ void uniform_u0_kernel(R *u, long long n, int d)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    u[2 * i] = (R)(-0.5 * log((double)d));
+    u[2 * i + 1] = (R)0;
+}
+
 // After phase 3 has stored the states of every chunk: the state at a reset step is the
 // reset one, which is the prefix entering the next chunk; also fills the per-step flags.
 struct ResetPostArgs {
@@ -508,6 +714,62 @@ int launch_reset_post(goom_ctx *ctx, const ResetLaunch &l)
     return check_hip(ctx, hipGetLastError(), "launch reset_post_kernel");
 }
 
+
+int launch_lyap_steps(goom_ctx *ctx, const void *J, const void *S0, const void *states, double *steplog, double *partial,
+                      double *lambda, long long T, int d, long long batch, double scale)
+{
+    StepArgs a;
+    a.J = static_cast<const float *>(J);
+    a.S0 = static_cast<const float *>(S0);
+    a.states = static_cast<const float *>(states);
+    a.steplog = steplog;
+    a.T = T;
+    a.d = d;
+    const long long grid = batch * T;
+    if (grid > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
+    const int dp = padded_dim(d);
+    prof_begin(ctx, "lyapunov_per_step_qr");
+    if (dp == 16)
+        hipLaunchKernelGGL(lyap_step_kernel<16>, dim3((unsigned)grid), dim3(64), 0, ctx->stream, a);
+    else if (dp == 32)
+        hipLaunchKernelGGL(lyap_step_kernel<32>, dim3((unsigned)grid), dim3(64), 0, ctx->stream, a);
+    else if (dp == 64)
+        hipLaunchKernelGGL(lyap_step_kernel<64>, dim3((unsigned)grid), dim3(64), 0, ctx->stream, a);
+    else
+        return fail(ctx, GOOM_EUNSUPPORTED, "the per-step estimator supports d <= 64 (d=%d)", d);
+    prof_end(ctx);
+    if (int st = check_hip(ctx, hipGetLastError(), "launch lyap_step_kernel")) return st;
+    prof_begin(ctx, "lyapunov_mean_of_logs");
+    hipLaunchKernelGGL(steplog_partial_kernel, dim3((unsigned)(batch * kSlices)), dim3(256), 0, ctx->stream, steplog, partial, T, d);
+    hipLaunchKernelGGL(steplog_final_kernel, dim3((unsigned)batch), dim3(64), 0, ctx->stream, partial, lambda, d, scale);
+    prof_end(ctx);
+    return check_hip(ctx, hipGetLastError(), "launch steplog kernels");
+}
+
+size_t lyap_steps_partial_bytes(long long batch, int d) { return align_up((size_t)batch * kSlices * d * sizeof(double), 256); }
+
+int launch_lle_epilogue(goom_ctx *ctx, const void *v, double *lle, long long batch, int d, int dtype, double scale)
+{
+    const unsigned blocks = (unsigned)((batch + 63) / 64);
+    prof_begin(ctx, "lle_log_norm");
+    if (dtype == GOOM_C64)
+        hipLaunchKernelGGL(lle_epilogue_kernel<float>, dim3(blocks), dim3(64), 0, ctx->stream, static_cast<const float *>(v), lle, batch, d, scale);
+    else
+        hipLaunchKernelGGL(lle_epilogue_kernel<double>, dim3(blocks), dim3(64), 0, ctx->stream, static_cast<const double *>(v), lle, batch, d, scale);
+    prof_end(ctx);
+    return check_hip(ctx, hipGetLastError(), "launch lle_epilogue_kernel");
+}
+
+int launch_uniform_u0(goom_ctx *ctx, void *u, long long batch, int d, int dtype)
+{
+    const long long n = batch * d;
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    if (dtype == GOOM_C64)
+        hipLaunchKernelGGL(uniform_u0_kernel<float>, dim3(blocks), dim3(256), 0, ctx->stream, static_cast<float *>(u), n, d);
+    else
+        hipLaunchKernelGGL(uniform_u0_kernel<double>, dim3(blocks), dim3(256), 0, ctx->stream, static_cast<double *>(u), n, d);
+    return check_hip(ctx, hipGetLastError(), "launch uniform_u0_kernel");
+}
 
 int launch_reset_carry(goom_ctx *ctx, const ResetLaunch &l)
 {

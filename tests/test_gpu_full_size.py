@@ -154,6 +154,16 @@ def test_config4_lyapunov_full_size(G, oracle):
     say(f"  max |lambda_gpu - lambda_qr| = {err.max():.2e} at k={int(err.argmax()) + 1}; lambda_1 = {lam[0]:.4f} "
         f"(QR {lam_qr[0]:.4f}), sum = {lam.sum():.4f} (QR {lam_qr.sum():.4f})")
     assert err.max() < 1e-3
+    # the paper's own pipeline (two QRs per step on the reset states) and the largest exponent alone
+    lam_ps = host(G.lyapunov_spectrum_per_step(Jz, dt))
+    lle = float(host(G.largest_lyapunov(Jz, dt)))
+    e1 = np.zeros(d)
+    e1[0] = 1.0
+    say(f"  per-step estimator: max |lambda - lambda_qr| = {np.abs(lam_ps - lam_qr).max():.2e}; "
+        f"largest exponent from the vector reduction {lle:.5f} (QR method {lam_qr[0]:.5f})")
+    assert np.abs(lam_ps - lam_qr).max() < 1e-3
+    u = np.full(d, 1.0 / math.sqrt(d))
+    assert abs(lle - oracle.lle_standard(Jr, u, dt)) < 1e-3
     # states, flags and growth of the reset scan on the same chain; the leading part against the
     # sequentially reset oracle, column by column (see the small cases for why not entry by entry)
     states, flags, growth = G.scan_reset(Jz)

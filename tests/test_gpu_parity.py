@@ -440,3 +440,65 @@ def test_lyapunov_spectrum_gaussian_closed_form(G, oracle):
     assert np.abs(lam - want).max() < 0.06
     lam_qr = oracle.lyapunov_qr(x.astype(np.float64), 1.0)
     assert np.abs(lam - lam_qr).max() < 1e-3
+
+
+# ------------------------------------ per-step estimator and largest exponent (Sections 4.2.1-4.2.2)
+
+@pytest.mark.parametrize("T,d,L,policy", [(2048, 32, 0, 1), (1000, 8, 16, 1), (600, 16, 7, 0), (300, 64, 16, 1)])
+def test_lyapunov_per_step_estimator(G, oracle, T, d, L, policy):
+    # groups (b)-(d): two QRs per step on the selectively reset states; against the same groups in the
+    # oracle (fed the oracle's own states) and against the sequential QR method
+    dt = 0.01
+    Jr = lorenz_chain(T, d, 71, burn_in=3000)
+    Jz = oracle.to_goom(Jr)
+    check = L if L > 0 else 32
+    re, sg, _, _ = oracle.reset_scan(Jz, None, check_every=check, policy=policy)
+    eye_re = np.where(np.eye(d) > 0, 0.0, -np.inf)
+    prev = (np.concatenate([eye_re[None], re[:-1]]), np.concatenate([np.zeros((1, d, d), np.uint8), sg[:-1]]))
+    lam_ref, logs_ref = oracle.lyapunov_from_states(prev, Jr, dt)
+    lam_qr = oracle.lyapunov_qr(Jr, dt)
+    lam, logs = G.lyapunov_spectrum_per_step(dev(Jz), dt, chunk_len=L, policy=policy, want_step_logs=True)
+    lam, logs = host(lam), host(logs)
+    say(f"per-step estimator T={T} d={d} L={L or 'default'} policy={policy}: max |gpu - oracle groups| = "
+        f"{np.abs(lam - lam_ref).max():.2e}, max |gpu - QR method| = {np.abs(lam - lam_qr).max():.2e}, "
+        f"worst single log R_kk off by {np.abs(logs - logs_ref).max():.2e}")
+    assert np.abs(lam - lam_ref).max() < 1e-3 and np.abs(lam - lam_qr).max() < 1e-3
+    # per step the logs add up to log|det J_t| whatever the basis; float QR keeps that to about 1e-4
+    dets = np.array([np.linalg.slogdet(j.astype(np.float64))[1] for j in Jr])
+    assert np.abs(logs.sum(axis=1) - dets).max() < 2e-3
+    # and the estimator that accumulates growth at the resets agrees
+    lam2 = host(G.lyapunov_spectrum(dev(Jz), dt, chunk_len=L, policy=1))
+    assert np.abs(lam - lam2).max() < 1e-3
+
+
+@pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
+def test_largest_lyapunov_exponent(G, oracle, ctype):
+    comp = np.float32 if ctype == np.complex64 else np.float64
+    dt = 0.01
+    for T, d, batch in ((4096, 32, 2), (700, 8, 3)):
+        Js, us, want, std = [], [], [], []
+        for b in range(batch):
+            Jr = lorenz_chain(T, d, 80 + b, burn_in=3000)
+            u0 = si.normal_f32(si.BASE_SEED + 90 + b, 4, d).astype(np.float64)
+            u0 /= np.linalg.norm(u0)
+            Jz, uz = oracle.to_goom(Jr.astype(comp)), oracle.to_goom(u0.astype(comp))
+            Js.append(Jz)
+            us.append(uz)
+            want.append(oracle.lle_goom(Jz, uz, dt, scaled=True))
+            std.append(oracle.lle_standard(Jr, u0, dt))
+        got = host(G.largest_lyapunov(dev(np.stack(Js)), dt, u0=dev(np.stack(us))))
+        say(f"LLE {np.dtype(ctype).name} T={T} d={d}: gpu {got}, oracle (eq. 17) {np.array(want)}, normalised iteration {np.array(std)}")
+        assert np.abs(got - np.array(want)).max() < 1e-3 and np.abs(got - np.array(std)).max() < 1e-3
+        # default start vector: all entries 1 / sqrt(d)
+        got0 = host(G.largest_lyapunov(dev(np.stack(Js)), dt))
+        u = np.full(d, 1.0 / math.sqrt(d))
+        ref0 = np.array([oracle.lle_standard(lorenz_chain(T, d, 80 + b, burn_in=3000), u, dt) for b in range(batch)])
+        assert np.abs(got0 - ref0).max() < 1e-3
+    # Gaussian factors far past float range: closed form (ln 2 + psi(d / 2)) / 2
+    from scipy.special import digamma
+    T, d = 20000, 16
+    Gz = oracle.to_goom(si.normal_chain(si.BASE_SEED + 95, T, d).astype(comp))
+    got = float(host(G.largest_lyapunov(dev(Gz), 1.0)))
+    lam = 0.5 * (math.log(2.0) + digamma(d / 2))
+    say(f"  Gaussian d={d}: {got:.5f} (closed form {lam:.5f}), log-norm {got * T:.0f}")
+    assert abs(got - lam) < 0.01 and got * T > 2.0e4
