@@ -130,7 +130,7 @@ def main():
         "config": {"workload": f"prefix scan of T={T} real {d}x{d} N(0,1) matrices as complex64 GOOMs, "
                                f"in HBM, {T * d * d * 8 / 1e9:.1f} GB in and out",
                    "T": T, "d": d, "chunk_len": args.chunk_len},
-        "lmme": {"tflops_executed": round(lmme_tflops, 2),
+        "lmme": {"tflops_executed": round(lmme_tflops, 2), "tflops_useful": round(lmme_tflops / 2, 2),
                  "pct_of_fp32_mfma_peak": round(100 * lmme_tflops / MFMA_F32_PEAK_TFLOPS, 2),
                  "per_phase_tflops": phase_tflops},
         "kernels_ms": {k: round(v, 4) for k, v in kern_avg.items()},
@@ -161,6 +161,12 @@ def main():
         torch.cuda.synchronize()
         cms = (time.perf_counter() - c0) / 3
         result["hbm_copy_gbs"] = round(2 * z.numel() * 8 / cms / 1e9, 1)
+        # what the float matrix units sustain on this machine for a plain library GEMM (8192^3, float32)
+        ga = torch.randn((8192, 8192), device=dev)
+        gb = torch.randn((8192, 8192), device=dev)
+        gsec = timed(torch, lambda: torch.mm(ga, gb), 5)
+        result["sgemm_tflops_measured"] = round(2 * 8192.0 ** 3 / gsec / 1e12, 1)
+        del ga, gb
 
     # ---- the other workloads of the same path, each timed on its own (not part of `value`)
     if not args.no_extras and not args.basic_extras:
