@@ -795,3 +795,25 @@ ORACLE_API double oracle_lle_from_final(const double *fre, long T, int d, double
     for (int i = 0; i < d; ++i) acc += expl((long double)(2.0 * fre[i] - m));
     return (double)(((long double)m + logl(acc)) / (2.0L * (long double)dt * (long double)T));
 }
+
+/* ------------------------------------------------------------------------- */
+/* scaled exponentiation of recurrence states (Section 4.3, eq. 21)           */
+/* ------------------------------------------------------------------------- */
+
+/* For each of n vectors of length d in working form: c = max of the log-magnitudes,
+ * scaled_i = (+-) exp(re_i - c + 2), so every scaled entry lies in [-e^2, e^2].  A vector of
+ * zeros has c = -inf and scaled = 0. */
+ORACLE_API void oracle_scaled_exp(const double *re, const uint8_t *sg, double *scaled, double *c, long n, int d)
+{
+    for (long v = 0; v < n; ++v) {
+        const double *r = re + (size_t)v * d;
+        double m = -INFINITY;
+        for (int i = 0; i < d; ++i)
+            if (r[i] > m) m = r[i];
+        c[v] = m;
+        for (int i = 0; i < d; ++i) {
+            double x = (m > -INFINITY) ? (double)expl((long double)r[i] - (long double)m + 2.0L) : 0.0;
+            scaled[(size_t)v * d + i] = sg[(size_t)v * d + i] ? -x : x;
+        }
+    }
+}

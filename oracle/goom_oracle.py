@@ -318,3 +318,15 @@ def lle_goom(jac, u0, dt: float, scaled: bool = False) -> float:
     f = lib().oracle_lle_from_final
     f.restype = C.c_double
     return float(f(_p(_c(fre.reshape(d), np.float64)), C.c_long(T), C.c_int(d), C.c_double(dt)))
+
+
+def scaled_exp(z):
+    """Scaled exponentiation of GOOM vectors over the last axis (Section 4.3, eq. 21):
+    returns (scaled reals in [-e^2, e^2], c = max log-magnitude of every vector)."""
+    re, sg = _as_working(z)
+    d = re.shape[-1]
+    n = int(np.prod(re.shape[:-1])) if re.ndim > 1 else 1
+    scaled = np.empty(re.shape, dtype=np.float64)
+    c = np.empty(re.shape[:-1], dtype=np.float64)
+    lib().oracle_scaled_exp(_p(re), _p(sg), _p(scaled), _p(c), C.c_long(n), C.c_int(d))
+    return scaled, c

@@ -263,3 +263,24 @@ def test_affine_degenerate_cases(oracle):
     re, sg = oracle.affine_scan(goom_of(np.full((T, 1, 1), a)), goom_of(np.full((T, 1), bb)))
     want = bb * (1 - a ** np.arange(1, T + 1)) / (1 - a)
     assert np.allclose(np.exp(re[:, 0]), want, rtol=1e-13) and np.all(sg == 0)
+
+
+def test_scaled_exponentiation_of_states(oracle):
+    # Section 4.3, eq. 21: c = max Re, scaled = exp(x' - c + 2): values within [-e^2, e^2], the largest
+    # entry exactly e^2 in magnitude, ratios of entries preserved, a common shift of the logs cancels
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((7, 12)) * np.exp(rng.uniform(-30, 30, (7, 12)))
+    z = oracle.to_goom(x)
+    s, c = oracle.scaled_exp(z)
+    assert np.allclose(c, np.log(np.abs(x).max(axis=1)), rtol=1e-15)
+    assert np.allclose(np.abs(s).max(axis=1), math.e ** 2, rtol=1e-14)
+    assert np.allclose(s, x / np.abs(x).max(axis=1, keepdims=True) * math.e ** 2, rtol=1e-12)
+    shifted = z + 5000.0  # far outside double range as reals
+    s2, c2 = oracle.scaled_exp(shifted)
+    assert np.allclose(s2, s, rtol=1e-12) and np.allclose(c2, c + 5000.0)
+    # the worked numbers: logs (0, -1, 1 + i pi) give c = 1 and (e, 1, -e^2)
+    s3, c3 = oracle.scaled_exp(np.array([0.0, -1.0, 1.0 + 1j * math.pi]))
+    assert c3 == 1.0 and np.allclose(s3, [math.e, 1.0, -math.e ** 2], rtol=1e-15)
+    # a vector of zeros stays zero
+    s4, c4 = oracle.scaled_exp(oracle.to_goom(np.zeros(3)))
+    assert np.all(s4 == 0) and np.isneginf(c4)
