@@ -226,6 +226,16 @@ size_t goom_largest_lyapunov_workspace_bytes(int64_t T, int d, int64_t batch, in
 
 /* ---- linear recurrence with bias (paper Section 4.3, eqs. 18 and 20) ---------------- */
 
+/* Scaled exponentiation of GOOM vectors (paper Section 4.3, eq. 21), the way recurrence states
+ * return to a floating-point format: for each of n_vectors vectors z[v, 0..d-1],
+ * c = max_i Re z[v, i] and scaled[v, i] = (+-) exp(Re z[v, i] - c + 2), so all results lie in
+ * [-e^2, e^2] whatever the magnitude of the state.  z: [n_vectors, d] GOOMs; scaled:
+ * [n_vectors, d] reals of the component type; logscale: NULL or [n_vectors] reals receiving c
+ * (-inf for a vector of zeros, whose scaled entries are 0). */
+int goom_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t n_vectors,
+                    int d, int dtype);
+
+
 /* h[b, t] = A[b, t] h[b, t-1] + bias[b, t], h[b, -1] = h0[b] (NULL = zero vector), over
  * GOOMs.  A: [batch, T, d, d]; bias: [batch, T, d]; h0: NULL or [batch, d];
  * H: [batch, T, d].  Scanned as products of the augmented matrices [A | bias; 0 | 1]

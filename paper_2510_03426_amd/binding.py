@@ -26,7 +26,7 @@ EXPORTS = [
     "goom_scan_reset", "goom_scan_reset_workspace_bytes", "goom_lyapunov_spectrum",
     "goom_lyapunov_spectrum_per_step", "goom_lyapunov_spectrum_per_step_workspace_bytes",
     "goom_largest_lyapunov", "goom_largest_lyapunov_workspace_bytes",
-    "goom_affine_scan", "goom_affine_scan_workspace_bytes",
+    "goom_affine_scan", "goom_affine_scan_workspace_bytes", "goom_scaled_exp",
 ]
 
 
@@ -92,6 +92,7 @@ def load_library():
     lib.goom_largest_lyapunov.argtypes = [vp, vp, vp, vp, i64, i32, C.c_double, i64, i32, po, vp, sz]
     lib.goom_largest_lyapunov_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_largest_lyapunov_workspace_bytes.restype = sz
+    lib.goom_scaled_exp.argtypes = [vp, vp, vp, vp, sz, i32, i32]
     lib.goom_affine_scan.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
     lib.goom_affine_scan_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_affine_scan_workspace_bytes.restype = sz
@@ -342,3 +343,15 @@ class Goom:
         self._check(self.lib.goom_largest_lyapunov(self._ctx, _ptr(jac), _ptr(u0), _ptr(lle), T, d, dt, batch, code,
                                                    C.byref(opts), _ptr(ws), wsn))
         return lle
+
+    def scaled_exp(self, z, want_logscale: bool = False):
+        """Scaled exponentiation over the last axis: exp(z - max Re z + 2), real."""
+        torch = self.torch
+        code = _dtype_code(z)
+        d = z.shape[-1]
+        nvec = z.numel() // d
+        comp = torch.float32 if z.dtype == torch.complex64 else torch.float64
+        out = torch.empty(z.shape, dtype=comp, device=z.device)
+        c = torch.empty(z.shape[:-1], dtype=comp, device=z.device) if want_logscale else None
+        self._check(self.lib.goom_scaled_exp(self._ctx, _ptr(z), _ptr(out), _ptr(c), nvec, d, code))
+        return (out, c) if want_logscale else out

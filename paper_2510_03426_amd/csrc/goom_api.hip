@@ -757,6 +757,18 @@ int goom_lyapunov_spectrum(goom_ctx *ctx, const void *J, const void *S0, void *s
                      workspace_bytes);
 }
 
+int goom_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t n_vectors, int d, int dtype)
+{
+    if (int s = check_common(ctx, dtype)) return s;
+    if (d <= 0) return fail(ctx, GOOM_EINVAL, "d must be positive");
+    if (n_vectors == 0) return ctx ? GOOM_OK : fail(nullptr, GOOM_EINVAL, "null context");
+    if (!z || !scaled) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    if (!aligned(z, 2 * comp_bytes(dtype)) || !aligned(scaled, comp_bytes(dtype)) || (logscale && !aligned(logscale, comp_bytes(dtype))))
+        return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
+    if (int s = need_ctx(ctx)) return s;
+    return launch_scaled_exp(ctx, z, scaled, logscale, n_vectors, d, dtype);
+}
+
 size_t goom_lyapunov_spectrum_per_step_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts,
                                                        int caller_has_states, int caller_has_step_logs)
 {

@@ -86,6 +86,42 @@ __global__ __launch_bounds__(256) void from_goom_f64_kernel(const double *__rest
     }
 }
 
+// Scaled exponentiation of GOOM vectors (paper Section 4.3, eq. 21): per vector of length d,
+// c = max of the log-magnitudes, scaled_i = (+-) exp(re_i - c + 2).  A group of G = 2^k >= d
+// lanes (at most 64) owns a vector when d <= 64, so the maximum is a few lane exchanges;
+// longer vectors take a whole wave and several elements per lane.  Evaluated in double and
+// rounded once, like the codecs.
+template <typename R, typename R2> __global__ __launch_bounds__(256) void scaled_exp_kernel(const R2 *__restrict__ z, R *__restrict__ out,
+                                                                                            R *__restrict__ cout, size_t nvec, int d, int group)
+{
+    const int lane = threadIdx.x & 63;
+    const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const size_t nwaves = ((size_t)gridDim.x * blockDim.x) >> 6;
+    const int per_wave = 64 / group; // vectors a wave handles at a time
+    const int sub = lane / group, el = lane % group;
+    const int reps = (d + group - 1) / group; // > 1 only when d > 64
+    for (size_t v0 = wave * per_wave; v0 < nvec; v0 += nwaves * per_wave) {
+        const size_t v = v0 + sub;
+        const bool live = v < nvec;
+        double m = -__builtin_huge_val();
+        for (int r = 0; r < reps; ++r) {
+            const int i = el + r * group;
+            if (live && i < d) m = fmax(m, (double)z[v * d + i].x);
+        }
+        for (int sft = 1; sft < group; sft <<= 1) m = fmax(m, __shfl_xor(m, sft, 64));
+        for (int r = 0; r < reps; ++r) {
+            const int i = el + r * group;
+            if (live && i < d) {
+                const R2 e = z[v * d + i];
+                double x = m > -__builtin_huge_val() ? exp((double)e.x - m + 2.0) : 0.0;
+                if (odd_multiple_of_pi((double)e.y)) x = -x;
+                out[v * d + i] = (R)x;
+            }
+        }
+        if (cout && live && el == 0) cout[v] = (R)m;
+    }
+}
+
 unsigned grid_for(size_t work_items)
 {
     size_t blocks = (work_items + 255) / 256;
@@ -113,6 +149,23 @@ int launch_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, u
     }
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch to_goom");
+}
+
+int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t nvec, int d, int dtype)
+{
+    if (nvec == 0) return GOOM_OK;
+    int group = 1;
+    while (group < d && group < 64) group <<= 1;
+    const size_t lanes = (nvec + (64 / group) - 1) / (64 / group) * 64;
+    prof_begin(ctx, "scaled_exp");
+    if (dtype == GOOM_C64)
+        hipLaunchKernelGGL((scaled_exp_kernel<float, float2>), dim3(grid_for(lanes)), dim3(256), 0, ctx->stream,
+                           static_cast<const float2 *>(z), static_cast<float *>(scaled), static_cast<float *>(logscale), nvec, d, group);
+    else
+        hipLaunchKernelGGL((scaled_exp_kernel<double, double2>), dim3(grid_for(lanes)), dim3(256), 0, ctx->stream,
+                           static_cast<const double2 *>(z), static_cast<double *>(scaled), static_cast<double *>(logscale), nvec, d, group);
+    prof_end(ctx);
+    return check_hip(ctx, hipGetLastError(), "launch scaled_exp");
 }
 
 int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype)

@@ -502,3 +502,36 @@ def test_largest_lyapunov_exponent(G, oracle, ctype):
     lam = 0.5 * (math.log(2.0) + digamma(d / 2))
     say(f"  Gaussian d={d}: {got:.5f} (closed form {lam:.5f}), log-norm {got * T:.0f}")
     assert abs(got - lam) < 0.01 and got * T > 2.0e4
+
+
+@pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
+def test_scaled_exponentiation(G, oracle, ctype):
+    # eq. 21 on states of a recurrence whose magnitudes leave float range, and on ragged shapes
+    comp = np.float32 if ctype == np.complex64 else np.float64
+    rng = np.random.default_rng(77)
+    for shape in ((3, 1000, 32), (513, 5), (70, 100), (2, 64), (9, 1)):
+        re = rng.normal(0.0, 400.0, shape)
+        z = (re + 1j * np.pi * rng.integers(0, 2, shape)).astype(ctype)
+        z.imag[...] = np.where(z.imag != 0, comp(np.pi), comp(0))
+        if shape[-1] > 2:
+            z.real[0, ..., 1] = -np.inf  # a zero entry
+        want, cw = oracle.scaled_exp(z)
+        got, c = G.scaled_exp(dev(z), want_logscale=True)
+        got, c = host(got), host(c)
+        assert np.array_equal(c, cw.astype(comp))
+        eps = np.finfo(comp).eps
+        # the argument re - c + 2 is formed in double on the device: its rounding, |argument| 2^-53,
+        # is the relative error of the exponential (visible only with double components)
+        arg = np.abs(np.where(np.isfinite(z.real), z.real - cw[..., None], 0.0))
+        assert np.all(np.abs(got - want) <= (4 * eps + 2.0 ** -52 * arg) * np.abs(want) + np.finfo(comp).tiny), np.abs(got - want).max()
+        assert np.abs(got).max() <= math.e ** 2 * (1 + 4 * eps)
+    zero = dev(np.full((4, 8), -np.inf + 0j).astype(ctype))
+    got, c = G.scaled_exp(zero, want_logscale=True)
+    assert np.all(host(got) == 0) and np.all(np.isneginf(host(c)))
+    # end to end: states of the recurrence, scaled
+    A, b = si.recurrence_inputs(si.BASE_SEED + 55, 2, 4000, 16, gain=1.3)
+    Az, bz = oracle.to_goom(A.astype(comp)), oracle.to_goom(b.astype(comp))
+    H = G.affine_scan(dev(Az), dev(bz))
+    want, _ = oracle.scaled_exp(host(H))
+    got = host(G.scaled_exp(H))
+    assert host(H).real.max() > 700 and np.all(np.abs(got - want) <= 4 * eps * np.abs(want) + np.finfo(comp).tiny)
