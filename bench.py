@@ -22,8 +22,8 @@ MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix rate, published
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--T", type=int, default=1 << 20)
     ap.add_argument("--d", type=int, default=64)
     ap.add_argument("--chunk-len", type=int, default=0)
@@ -32,6 +32,8 @@ def main():
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs")
     ap.add_argument("--no-extras", action="store_true", help="time the headline scan only")
+    ap.add_argument("--only", choices=["tiny", "scan128", "lmme", "lyapunov", "recurrence"], default=None,
+                    help="time just one of the other workloads (for profiler runs) and print its figures")
     ap.add_argument("--basic-extras", action="store_true",
                     help="besides the scan, time only a plain device copy of the same size (for counter runs)")
     args = ap.parse_args()
@@ -48,6 +50,10 @@ def main():
     T, d = args.T, args.d
     dev = torch.device("cuda", 0)
     g = Goom(0)
+
+    if args.only:
+        print(json.dumps({"other_workloads": other_workloads(g, torch, dev, args.only)}), flush=True)
+        return
 
     # ---- synthetic input: N(0,1) reals drawn on the device, encoded by the library's codec
     gen = torch.Generator(device=dev)
@@ -216,18 +222,33 @@ def kernel_times(g, fn):
     return per
 
 
-def other_workloads(g, torch, dev):
+def other_workloads(g, torch, dev, only=None):
     """Scan of 128 x 128 matrices, batched LMME, Lyapunov spectrum, non-diagonal recurrence, tiny scan."""
-    import math
     import synthetic_inputs as si
-    from paper_2510_03426_amd import LMME_EXACT, LMME_FAST
     res = {}
+    want = lambda name: only is None or only == name
+    if want("tiny"):
+        res["scan_T256_d8"] = tiny_scan(g, torch, dev, si)
+    if want("scan128"):
+        res.update(scan128(g, torch, dev, si))
+    if want("lmme"):
+        res.update(batched_lmme(g, torch, dev, si))
+    if want("lyapunov"):
+        res.update(lyapunov(g, torch, dev, si))
+    if want("recurrence"):
+        res.update(recurrence(g, torch, dev, si))
+    return res
 
+
+def tiny_scan(g, torch, dev, si):
     # tiny scan (T = 256, d = 8): latency of one call
     zt = g.to_goom(torch.randn((256, 8, 8), device=dev, generator=si.device_generator(11, dev)))
-    res["scan_T256_d8"] = {"us_per_scan": round(timed(torch, lambda: g.scan(zt), 50) * 1e6, 1)}
+    return {"us_per_scan": round(timed(torch, lambda: g.scan(zt), 50) * 1e6, 1)}
 
+
+def scan128(g, torch, dev, si):
     # scan of 128 x 128 matrices, T = 262,144 (same bytes as the headline workload)
+    res = {}
     T, d = 1 << 18, 128
     z = torch.empty((T, d, d), dtype=torch.complex64, device=dev)
     for t0, x in si.device_normal_blocks(251003426 * 10 + 3, T, (d, d), dev, 1 << 14):
@@ -242,8 +263,13 @@ def other_workloads(g, torch, dev):
         "kernels_ms": kernel_times(g, lambda: g.scan(z, out=out))}
     del z, out
     torch.cuda.empty_cache()
+    return res
 
+
+def batched_lmme(g, torch, dev, si):
     # batched LMME: 8192 pairs of 128 x 128, log-magnitudes N(0, 200^2)
+    from paper_2510_03426_amd import LMME_EXACT, LMME_FAST
+    res = {}
     B, n = 8192, 128
     for ctype, name in ((torch.complex64, "c64"), (torch.complex128, "c128")):
         a = si.device_wide_range_gooms(251003426 * 10 + 31, (B, n, n), 200.0, ctype, dev)
@@ -267,8 +293,12 @@ def other_workloads(g, torch, dev):
             "hbm_gbs": round(3 * a.numel() * a.element_size() / sec / 1e9, 1)}
         del a, b, c
         torch.cuda.empty_cache()
+    return res
 
+
+def lyapunov(g, torch, dev, si):
     # Lyapunov spectrum of Lorenz-96 (d = 32) over T = 131,072 Jacobians, resets every 32 steps
+    res = {}
     T, d = 131072, 32
     Jr, _ = si.lorenz96_jacobians(si.BASE_SEED + 4, T, d=d, burn_in=10000)
     Jz = g.to_goom(torch.from_numpy(Jr).to(dev))
@@ -293,8 +323,13 @@ def other_workloads(g, torch, dev):
         "ms": round(sec * 1e3, 3), "jacobians_per_s": round(T / sec, 1),
         "kernels_ms": kernel_times(g, lambda: g.scan_reset(Jz))}
     del Jz
+    return res
 
+
+def recurrence(g, torch, dev, si):
     # non-diagonal recurrence: 8 x 16 sequences of 65,536 tokens, d = 32
+    import math
+    res = {}
     nseq, T, d = 128, 65536, 32
     az = torch.empty((nseq, T, d, d), dtype=torch.complex64, device=dev)
     for s0, x in si.device_normal_blocks(251003426 * 10 + 51, nseq, (T, d, d), dev, 4, scale=1.05 / math.sqrt(d)):
