@@ -167,14 +167,15 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) voi
 #pragma unroll
             for (int v = 0; v < 4; ++v) cmax = C::max_(cmax, gp[((size_t)(16 * kt + 4 * g + v) * M + col) * 2]);
         cmax = C::xor16_32_max(cmax);
-        ecol = (cmax > C::neg_inf()) ? __builtin_ceil((double)cmax * kLog2e) : 0.0;
+        // the column's exponent: a whole number near its largest log2 magnitude that a float holds exactly
+        const float ecol_f = (cmax > C::neg_inf()) ? (float)__builtin_ceil((double)cmax * kLog2e) : 0.0f;
+        ecol = (double)ecol_f;
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float *e = gp + ((size_t)(16 * kt + 4 * g + v) * M + col) * 2;
-                const float x = exp2_of<float>(__builtin_fma((double)e[0], kLog2e, -ecol));
-                st[kt][v] = C::apply_sign(x, e[1]);
+                const float2 e = *reinterpret_cast<const float2 *>(gp + ((size_t)(16 * kt + 4 * g + v) * M + col) * 2);
+                st[kt][v] = C::apply_sign(C::exp2_shifted(e.x, ecol_f), e.y);
             }
     }
 
@@ -182,7 +183,7 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) voi
     if (len > 0 && converter) {
         load_items(0, pre);
         convert_items(pre, 0, nullptr);
-        load_items(len > 1 ? 1 : 0, pre);
+        if (len > 1) load_items(1, pre);
     }
     // bias vector of a step, rows 16 kt + 4 g + v of this lane: (re, im) pairs, two 16-byte loads per kt
     f4 bpre[BIAS ? KT : 1][2];
@@ -218,9 +219,9 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) voi
 #pragma unroll
                 for (int mt = 0; mt < KT; ++mt) acc[mt] = C::mfma(av[mt][v], st[kt][v], acc[mt]);
         }
-        // Past the end of the chain the last factor is converted and loaded once more
-        // (clamped index) rather than branching; nobody reads the result.
-        if (converter) {
+        // (after the last product there is nothing to convert: a single product, as in a
+        // batched LMME, would otherwise pay for its left factor twice)
+        if (converter && !last) {
             convert_items(pre, cur ^ 1, nsh);
             load_items(t + 2 < len ? t + 2 : len - 1, pre);
         }
