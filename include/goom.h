@@ -226,6 +226,11 @@ size_t goom_largest_lyapunov_workspace_bytes(int64_t T, int d, int64_t batch, in
 
 /* ---- linear recurrence with bias (paper Section 4.3, eqs. 18 and 20) ---------------- */
 
+/* Signed log-add, elementwise: out[i] is the GOOM of exp(x[i]) + exp(y[i]) (paper Section 2,
+ * Example 2; the step that adds the input term in eq. 20).  x, y, out: n GOOMs each; out may
+ * alias x or y.  Equal magnitudes of opposite sign give zero, (-inf, 0). */
+int goom_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, size_t n, int dtype);
+
 /* Scaled exponentiation of GOOM vectors (paper Section 4.3, eq. 21), the way recurrence states
  * return to a floating-point format: for each of n_vectors vectors z[v, 0..d-1],
  * c = max_i Re z[v, i] and scaled[v, i] = (+-) exp(Re z[v, i] - c + 2), so all results lie in

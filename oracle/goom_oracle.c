@@ -817,3 +817,35 @@ ORACLE_API void oracle_scaled_exp(const double *re, const uint8_t *sg, double *s
         }
     }
 }
+
+/* ------------------------------------------------------------------------- */
+/* signed log-add of two GOOM arrays: log(exp(x') + exp(y')) (Section 2, Example 2; */
+/* the bias step of Section 4.3, eq. 20)                                      */
+/* ------------------------------------------------------------------------- */
+
+/* Elementwise.  With m the larger and l the smaller log-magnitude, delta = m - l >= 0:
+ * same signs: m + log1p(exp(-delta)); opposite signs: m + log(-expm1(-delta)), sign of the
+ * larger; equal magnitudes with opposite signs give zero (-inf, +). */
+ORACLE_API void oracle_log_add_exp(const double *xre, const uint8_t *xsg, const double *yre, const uint8_t *ysg,
+                                   double *ore, uint8_t *osg, long n)
+{
+#pragma omp parallel for schedule(static)
+    for (long i = 0; i < n; ++i) {
+        double a = xre[i], b = yre[i];
+        uint8_t sa = xsg[i], sb = ysg[i];
+        if (b > a || (b == a && sb < sa)) { double t = a; a = b; b = t; uint8_t u = sa; sa = sb; sb = u; }
+        if (!(a > -INFINITY)) { ore[i] = -INFINITY; osg[i] = 0; continue; }       /* 0 + 0 */
+        if (!(b > -INFINITY)) { ore[i] = a; osg[i] = sa; continue; }               /* x + 0 */
+        long double delta = (long double)a - (long double)b;
+        if (sa == sb) {
+            ore[i] = (double)((long double)a + log1pl(expl(-delta)));
+            osg[i] = sa;
+        } else if (delta == 0.0L) {
+            ore[i] = -INFINITY;
+            osg[i] = 0;
+        } else {
+            ore[i] = (double)((long double)a + logl(-expm1l(-delta)));
+            osg[i] = sa;
+        }
+    }
+}

@@ -330,3 +330,14 @@ def scaled_exp(z):
     c = np.empty(re.shape[:-1], dtype=np.float64)
     lib().oracle_scaled_exp(_p(re), _p(sg), _p(scaled), _p(c), C.c_long(n), C.c_int(d))
     return scaled, c
+
+
+def log_add_exp(x, y):
+    """Elementwise signed log-add of two GOOM arrays: the GOOM of exp(x) + exp(y).  Returns (re, sg)."""
+    xre, xsg = _as_working(x)
+    yre, ysg = _as_working(y)
+    assert xre.shape == yre.shape
+    ore = np.empty(xre.shape, dtype=np.float64)
+    osg = np.empty(xre.shape, dtype=np.uint8)
+    lib().oracle_log_add_exp(_p(xre), _p(xsg), _p(yre), _p(ysg), _p(ore), _p(osg), C.c_long(xre.size))
+    return ore, osg

@@ -26,7 +26,7 @@ EXPORTS = [
     "goom_scan_reset", "goom_scan_reset_workspace_bytes", "goom_lyapunov_spectrum",
     "goom_lyapunov_spectrum_per_step", "goom_lyapunov_spectrum_per_step_workspace_bytes",
     "goom_largest_lyapunov", "goom_largest_lyapunov_workspace_bytes",
-    "goom_affine_scan", "goom_affine_scan_workspace_bytes", "goom_scaled_exp",
+    "goom_affine_scan", "goom_affine_scan_workspace_bytes", "goom_scaled_exp", "goom_log_add_exp",
 ]
 
 
@@ -93,6 +93,7 @@ def load_library():
     lib.goom_largest_lyapunov_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_largest_lyapunov_workspace_bytes.restype = sz
     lib.goom_scaled_exp.argtypes = [vp, vp, vp, vp, sz, i32, i32]
+    lib.goom_log_add_exp.argtypes = [vp, vp, vp, vp, sz, i32]
     lib.goom_affine_scan.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
     lib.goom_affine_scan_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_affine_scan_workspace_bytes.restype = sz
@@ -355,3 +356,11 @@ class Goom:
         c = torch.empty(z.shape[:-1], dtype=comp, device=z.device) if want_logscale else None
         self._check(self.lib.goom_scaled_exp(self._ctx, _ptr(z), _ptr(out), _ptr(c), nvec, d, code))
         return (out, c) if want_logscale else out
+
+    def log_add_exp(self, x, y, out=None):
+        """Elementwise GOOM of exp(x) + exp(y)."""
+        assert x.shape == y.shape and x.dtype == y.dtype
+        if out is None:
+            out = self.torch.empty_like(x)
+        self._check(self.lib.goom_log_add_exp(self._ctx, _ptr(x), _ptr(y), _ptr(out), x.numel(), _dtype_code(x)))
+        return out

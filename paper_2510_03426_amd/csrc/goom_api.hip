@@ -757,6 +757,17 @@ int goom_lyapunov_spectrum(goom_ctx *ctx, const void *J, const void *S0, void *s
                      workspace_bytes);
 }
 
+int goom_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, size_t n, int dtype)
+{
+    if (int s = check_common(ctx, dtype)) return s;
+    if (n == 0) return ctx ? GOOM_OK : fail(nullptr, GOOM_EINVAL, "null context");
+    if (!x || !y || !out) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    const size_t al = 2 * comp_bytes(dtype);
+    if (!aligned(x, al) || !aligned(y, al) || !aligned(out, al)) return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
+    if (int s = need_ctx(ctx)) return s;
+    return launch_log_add_exp(ctx, x, y, out, n, dtype);
+}
+
 int goom_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t n_vectors, int d, int dtype)
 {
     if (int s = check_common(ctx, dtype)) return s;

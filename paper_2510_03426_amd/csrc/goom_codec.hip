@@ -122,6 +122,47 @@ template <typename R, typename R2> __global__ __launch_bounds__(256) void scaled
     }
 }
 
+// Signed log-add of two GOOM arrays: the GOOM of exp(x') + exp(y') (paper Section 2, Example 2; the
+// bias step of eq. 20).  In double, rounded once: with m the larger log-magnitude and delta the gap,
+// m + log1p(exp(-delta)) for equal signs, m + log(-expm1(-delta)) for opposite ones.
+template <typename R, typename R2> __global__ __launch_bounds__(256) void log_add_exp_kernel(const R2 *__restrict__ x, const R2 *__restrict__ y,
+                                                                                             R2 *__restrict__ out, size_t n, R pi)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const R2 p = x[i], q = y[i];
+        double a = (double)p.x, b = (double)q.x;
+        bool sa = odd_multiple_of_pi((double)p.y), sb = odd_multiple_of_pi((double)q.y);
+        if (b > a || (b == a && !sb && sa)) {
+            const double t = a; a = b; b = t;
+            const bool u = sa; sa = sb; sb = u;
+        }
+        double re;
+        bool neg = sa;
+        const double ninf = -__builtin_huge_val();
+        if (!(a > ninf)) {
+            re = ninf;
+            neg = false;
+        } else if (!(b > ninf)) {
+            re = a;
+        } else {
+            const double delta = a - b;
+            if (sa == sb) {
+                re = a + log1p(exp(-delta));
+            } else if (delta == 0.0) {
+                re = ninf;
+                neg = false;
+            } else {
+                re = a + log(-expm1(-delta));
+            }
+        }
+        R2 o;
+        o.x = (R)re;
+        o.y = neg ? pi : (R)0;
+        out[i] = o;
+    }
+}
+
 unsigned grid_for(size_t work_items)
 {
     size_t blocks = (work_items + 255) / 256;
@@ -166,6 +207,20 @@ int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale
                            static_cast<const double2 *>(z), static_cast<double *>(scaled), static_cast<double *>(logscale), nvec, d, group);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch scaled_exp");
+}
+
+int launch_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, size_t n, int dtype)
+{
+    if (n == 0) return GOOM_OK;
+    prof_begin(ctx, "log_add_exp");
+    if (dtype == GOOM_C64)
+        hipLaunchKernelGGL((log_add_exp_kernel<float, float2>), dim3(grid_for(n)), dim3(256), 0, ctx->stream, static_cast<const float2 *>(x),
+                           static_cast<const float2 *>(y), static_cast<float2 *>(out), n, 3.14159274101257324219f);
+    else
+        hipLaunchKernelGGL((log_add_exp_kernel<double, double2>), dim3(grid_for(n)), dim3(256), 0, ctx->stream, static_cast<const double2 *>(x),
+                           static_cast<const double2 *>(y), static_cast<double2 *>(out), n, 3.14159265358979311600);
+    prof_end(ctx);
+    return check_hip(ctx, hipGetLastError(), "launch log_add_exp");
 }
 
 int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype)

@@ -535,3 +535,29 @@ def test_scaled_exponentiation(G, oracle, ctype):
     want, _ = oracle.scaled_exp(host(H))
     got = host(G.scaled_exp(H))
     assert host(H).real.max() > 700 and np.all(np.abs(got - want) <= 4 * eps * np.abs(want) + np.finfo(comp).tiny)
+
+
+@pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
+def test_signed_log_add(G, oracle, ctype):
+    comp = np.float32 if ctype == np.complex64 else np.float64
+    rng = np.random.default_rng(78)
+    n = (1 << 18) + 5
+    def gooms(scale):
+        z = (rng.normal(0.0, scale, n) + 1j * np.pi * rng.integers(0, 2, n)).astype(ctype)
+        z.imag[...] = np.where(z.imag != 0, comp(np.pi), comp(0))
+        return z
+    x, y = gooms(300.0), gooms(300.0)
+    y[:1000] = x[:1000]                      # equal magnitudes: doubling or exact cancellation
+    y[1000:2000].real = x[1000:2000].real + comp(1e-3) * rng.standard_normal(1000).astype(comp)  # near cancellation
+    x[2000:2010].real = -np.inf              # zero operands
+    y[2005:2015].real = -np.inf
+    re, sg = oracle.log_add_exp(x, y)
+    got = host(G.log_add_exp(dev(x), dev(y)))
+    assert np.array_equal(got.imag != 0, sg.astype(bool))
+    assert np.all((got.imag == 0) | (got.imag == comp(np.pi)))
+    want = re.astype(comp)
+    fin = np.isfinite(want)
+    assert np.array_equal(np.isneginf(got.real), np.isneginf(want))
+    ulp = np.abs(got.real[fin].astype(np.float64) - want[fin].astype(np.float64)) / np.spacing(np.abs(want[fin])).astype(np.float64)
+    say(f"log-add {np.dtype(ctype).name}: {np.sum(got.real[fin] != want[fin])} of {fin.sum()} results differ from the rounded oracle, max {ulp.max():.1f} ulp")
+    assert ulp.max() <= (1.0 if comp == np.float32 else 4.0)

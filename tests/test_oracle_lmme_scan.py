@@ -284,3 +284,36 @@ def test_scaled_exponentiation_of_states(oracle):
     # a vector of zeros stays zero
     s4, c4 = oracle.scaled_exp(oracle.to_goom(np.zeros(3)))
     assert np.all(s4 == 0) and np.isneginf(c4)
+
+
+def test_signed_log_add(oracle):
+    # the GOOM of a sum: against plain addition where everything is in range, and its algebra where not
+    rng = np.random.default_rng(8)
+    a = rng.standard_normal(2000) * np.exp(rng.uniform(-20, 20, 2000))
+    b = rng.standard_normal(2000) * np.exp(rng.uniform(-20, 20, 2000))
+    re, sg = oracle.log_add_exp(oracle.to_goom(a), oracle.to_goom(b))
+    s = a + b
+    # the logs of a and b are rounded to double: each carries a relative error of |log| * 2^-53 into the sum
+    slack = (np.abs(np.log(np.abs(a))) * np.abs(a) + np.abs(np.log(np.abs(b))) * np.abs(b)) / np.abs(s) * 2.0 ** -52
+    assert np.all(np.abs(re - np.log(np.abs(s))) <= 1e-15 * np.abs(re) + slack + 1e-15) and np.array_equal(sg, (s < 0).astype(np.uint8))
+    re2, sg2 = oracle.log_add_exp(oracle.to_goom(b), oracle.to_goom(a))
+    assert np.array_equal(re, re2) and np.array_equal(sg, sg2)  # commutative, bit for bit
+    # far outside any float range: e^1000 + e^1000 = e^(1000 + ln 2); e^1000 - e^1000 = 0; x + 0 = x
+    big = np.array([1000.0 + 0j, 1000.0 + 0j, 1000.0 + 1j * math.pi, -np.inf + 0j, -5000.0 + 0j])
+    other = np.array([1000.0 + 0j, 1000.0 + 1j * math.pi, 999.0 + 0j, 3.0 + 1j * math.pi, -5000.0 + 1j * math.pi])
+    re, sg = oracle.log_add_exp(big, other)
+    assert abs(re[0] - (1000.0 + math.log(2.0))) < 1e-12 and sg[0] == 0
+    assert np.isneginf(re[1]) and sg[1] == 0
+    assert abs(re[2] - (1000.0 + math.log(1.0 - math.exp(-1.0)))) < 1e-12 and sg[2] == 1
+    assert re[3] == 3.0 and sg[3] == 1
+    assert np.isneginf(re[4])
+    # it is the two-term case of the signed log-sum-exp that defines LMME: a 1 x 2 times 2 x 1 product
+    for k in range(20):
+        A = np.array([[oracle.to_goom(a[k:k + 1])[0], oracle.to_goom(b[k:k + 1])[0]]])
+        ones = np.zeros((2, 1), dtype=np.complex128)
+        r1, s1 = oracle.lmme(A, ones)
+        assert abs(r1[0, 0] - re_k(oracle, a[k], b[k])) < 1e-13 and s1[0, 0] == (a[k] + b[k] < 0)
+
+
+def re_k(oracle, x, y):
+    return oracle.log_add_exp(oracle.to_goom(np.array([x])), oracle.to_goom(np.array([y])))[0][0]
