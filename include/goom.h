@@ -129,7 +129,7 @@ size_t goom_lmme_workspace_bytes(int64_t batch, int n, int d, int m, int dtype, 
 
 typedef struct goom_scan_opts {
     int64_t chunk_len; /* matrices per chunk of the three-phase scan; 0 = library default */
-    uint32_t flags;    /* reserved, must be 0 */
+    uint32_t flags;    /* 0, or GOOM_AFFINE_TIME_INVARIANT for goom_affine_scan */
 } goom_scan_opts;
 
 /* Inclusive prefix products, newer factor on the left (paper eq. 9):
@@ -246,6 +246,9 @@ int goom_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, 
  * H: [batch, T, d].  Scanned as products of the augmented matrices [A | bias; 0 | 1]
  * whose last row is kept implicit.
  * workspace: goom_affine_scan_workspace_bytes(...) bytes. */
+#define GOOM_AFFINE_TIME_INVARIANT 0x1u /* goom_scan_opts.flags: one matrix per batch item, A: [batch, d, d],
+                                           applied at every step (the paper's state-space layer has constant
+                                           A); it is encoded once and its powers serve all chunks */
 int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H,
                      int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts,
                      void *workspace, size_t workspace_bytes);

@@ -6,5 +6,5 @@ and a gfx950 device every call raises.
 """
 from .binding import (  # noqa: F401
     GoomError, Goom, C64, C128, ZERO_NEG_INF, ZERO_FLOOR, LMME_FAST, LMME_EXACT,
-    RESET_ALWAYS, RESET_COLINEAR, RESET_NEVER, library_path, load_library,
+    RESET_ALWAYS, RESET_COLINEAR, RESET_NEVER, AFFINE_TIME_INVARIANT, library_path, load_library,
 )

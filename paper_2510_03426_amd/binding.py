@@ -18,6 +18,7 @@ C64, C128 = 0, 1
 ZERO_NEG_INF, ZERO_FLOOR = 0, 1
 LMME_FAST, LMME_EXACT = 0, 1
 RESET_ALWAYS, RESET_COLINEAR, RESET_NEVER = 1, 0, -1
+AFFINE_TIME_INVARIANT = 1
 
 EXPORTS = [
     "goom_version", "goom_create", "goom_destroy", "goom_set_stream", "goom_last_error",
@@ -259,16 +260,17 @@ class Goom:
                                          C.byref(opts), _ptr(ws), wsn))
         return out
 
-    def affine_scan(self, a, bias, h0=None, chunk_len: int = 0, out=None):
+    def affine_scan(self, a, bias, h0=None, chunk_len: int = 0, out=None, time_invariant: bool = False):
+        """h_t = A_t h_{t-1} + bias_t.  a: [..., T, d, d], or [..., d, d] with time_invariant=True."""
         torch = self.torch
         code = _dtype_code(a)
         T, d = bias.shape[-2:]
         lead = bias.shape[:-2]
-        assert a.shape == lead + (T, d, d) and a.dtype == bias.dtype
+        assert a.shape == (lead + (d, d) if time_invariant else lead + (T, d, d)) and a.dtype == bias.dtype
         batch = 1
         for s in lead:
             batch *= s
-        opts = ScanOpts(chunk_len, 0)
+        opts = ScanOpts(chunk_len, AFFINE_TIME_INVARIANT if time_invariant else 0)
         if out is None:
             out = torch.empty(lead + (T, d), dtype=a.dtype, device=a.device)
         ws, wsn = self.workspace(self.lib.goom_affine_scan_workspace_bytes(T, d, batch, code, C.byref(opts)))

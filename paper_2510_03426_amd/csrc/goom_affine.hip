@@ -26,7 +26,9 @@ template <int CTRL> __device__ inline float add_dpp(float x)
 
 constexpr int kWalkWaves = 4; // chunks per workgroup
 
-template <int DP> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk_kernel(ChainArgs a, long long nchains)
+// TI: the same matrix at every step (a time-invariant recurrence): it is loaded and scaled once,
+// and a step is a few multiply-adds per lane on registers.
+template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk_kernel(ChainArgs a, long long nchains)
 {
     typedef Comp<float> C;
     constexpr int LPR = DP / 4;   // lanes that share a row
@@ -51,53 +53,52 @@ template <int DP> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk
     if (len <= 0) return;
     const unsigned char *left0 = a.left + item * a.left_batch_stride + t0 * a.left_step_stride;
     const float *bias0 = reinterpret_cast<const float *>(a.bias) + (size_t)(item * a.steps + t0) * DP * 2;
-    float *out0 = reinterpret_cast<float *>(a.out_goom) + (size_t)(item * a.steps + t0) * DP * 2;
+    float *out0 = a.out_goom ? reinterpret_cast<float *>(a.out_goom) + (size_t)(item * a.steps + t0) * DP * 2 : nullptr;
 
-    // carried vector: column 0 of a factored state
-    long long iidx = item * a.chunks_per_item + chunk;
-    if (a.init_group > 0) {
-        long long grp = chunk / a.init_group;
-        if (grp >= a.init_ngroups) grp = a.init_ngroups - 1;
-        iidx = (item * a.init_ngroups + grp) * (a.init_group + 1) + (chunk - grp * a.init_group);
-    }
-    const unsigned char *ip = a.init + iidx * a.init_stride;
-    const float *mp = reinterpret_cast<const float *>(ip);
-    double eh = *reinterpret_cast<const double *>(ip + (size_t)DP * a.fact_cols * sizeof(float));
-    f4 hm;
+    // starting vector: zero, or column 0 of a factored carry
+    f4 hm = {0.f, 0.f, 0.f, 0.f};
+    double eh = 0.0;
+    if (a.init_mode == 1) {
+        long long iidx = item * a.chunks_per_item + chunk;
+        if (a.init_group > 0) {
+            long long grp = chunk / a.init_group;
+            if (grp >= a.init_ngroups) grp = a.init_ngroups - 1;
+            iidx = (item * a.init_ngroups + grp) * (a.init_group + 1) + (chunk - grp * a.init_group);
+        }
+        const unsigned char *ip = a.init + iidx * a.init_stride;
+        const float *mp = reinterpret_cast<const float *>(ip);
+        eh = *reinterpret_cast<const double *>(ip + (size_t)DP * a.fact_cols * sizeof(float));
 #pragma unroll
-    for (int e = 0; e < 4; ++e) hm[e] = mp[(size_t)(c4 + e) * a.fact_cols];
-    {   // a zero vector carries no meaningful exponent
+        for (int e = 0; e < 4; ++e) hm[e] = mp[(size_t)(c4 + e) * a.fact_cols];
+        // a zero vector carries no meaningful exponent
         const bool nz = hm[0] != 0.0f || hm[1] != 0.0f || hm[2] != 0.0f || hm[3] != 0.0f;
         if (__builtin_amdgcn_ballot_w64(nz) == 0 || !(__builtin_fabs(eh) < 1.0e15)) eh = 0.0;
     }
 
     Item4 cur[Q], nxt[Q];
     float2 bcur[Q], bnxt[Q];
-    auto load_step = [&](long long t, Item4 (&it)[Q], float2 (&bb)[Q]) {
+    auto load_matrix = [&](long long t, Item4 (&it)[Q]) {
         const float *src = reinterpret_cast<const float *>(left0 + t * a.left_step_stride);
-        const float *bsrc = bias0 + (size_t)t * DP * 2;
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            const int row = q * RPP + rsub;
-            const f4 *gp = reinterpret_cast<const f4 *>(src + ((size_t)row * DP + c4) * 2);
+            const f4 *gp = reinterpret_cast<const f4 *>(src + ((size_t)(q * RPP + rsub) * DP + c4) * 2);
             it[q].a = gp[0];
             it[q].b = gp[1];
-            bb[q] = *reinterpret_cast<const float2 *>(bsrc + (size_t)row * 2);
         }
     };
-    load_step(0, cur, bcur);
-
-    const float kHi = 1.44269502162933349609375f; // float nearest log2(e)
-    const float kLo = 1.925963033500011e-8f;      // log2(e) - kHi
-    for (long long t = 0; t < len; ++t) {
-        load_step(t + 1 < len ? t + 1 : len - 1, nxt, bnxt);
-        const float eh_f = (float)eh;
-        float val[Q], nrow[Q], barg[Q];
-        float bmax = -1.0e30f;
+    auto load_bias = [&](long long t, float2 (&bb)[Q]) {
+        const float *bsrc = bias0 + (size_t)t * DP * 2;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) bb[q] = *reinterpret_cast<const float2 *>(bsrc + (size_t)(q * RPP + rsub) * 2);
+    };
+    // the lane's entries of every row, scaled by the row's power of two and signed; the row shifts
+    float sv[Q][4], nrow[Q];
+    auto scale_rows = [&](const Item4 (&it)[Q]) {
+        const float kHi = 1.44269502162933349609375f; // float nearest log2(e)
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            const float re[4] = {cur[q].a[0], cur[q].a[2], cur[q].b[0], cur[q].b[2]};
-            const float im[4] = {cur[q].a[1], cur[q].a[3], cur[q].b[1], cur[q].b[3]};
+            const float re[4] = {it[q].a[0], it[q].a[2], it[q].b[0], it[q].b[2]};
+            const float im[4] = {it[q].a[1], it[q].a[3], it[q].b[1], it[q].b[3]};
             // row shift: a whole number near the row's largest log2|A_ij|
             float u = vmax_raw(vmax_raw(re[0], re[1]), vmax_raw(re[2], re[3])) * kHi;
             int key = C::key_of(u);
@@ -109,25 +110,44 @@ template <int DP> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk
             const bool zero_row = !(mx > -1.0e30f);
             const float n = zero_row ? 0.0f : __builtin_ceilf(mx);
             const float nsub = zero_row ? __builtin_huge_valf() : n;
-            float part = 0.0f;
+            nrow[q] = n;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 // (this kernel waits on memory, so the entries get the exponential that is good to
                 // a few units in the last place at any shift rather than the cheapest one)
                 const float v = C::exp2_shifted(re[e], nsub);
                 const float kf = __builtin_fmaf(im[e], 0.318309886183790671538f, 12582912.0f);
-                const float sv = __builtin_bit_cast(float, __builtin_bit_cast(int, v) ^ (__builtin_bit_cast(int, kf) << 31));
-                part = __builtin_fmaf(sv, hm[e], part);
+                sv[q][e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) ^ (__builtin_bit_cast(int, kf) << 31));
             }
+        }
+    };
+    load_matrix(0, cur);
+    load_bias(0, bcur);
+    if (TI) scale_rows(cur);
+
+    const float kHi = 1.44269502162933349609375f; // float nearest log2(e)
+    const float kLo = 1.925963033500011e-8f;      // log2(e) - kHi
+    for (long long t = 0; t < len; ++t) {
+        const long long tn = t + 1 < len ? t + 1 : len - 1;
+        if (!TI) load_matrix(tn, nxt);
+        load_bias(tn, bnxt);
+        if (!TI) scale_rows(cur);
+        const float eh_f = (float)eh;
+        float val[Q], barg[Q];
+        float bmax = -1.0e30f;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            float part = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) part = __builtin_fmaf(sv[q][e], hm[e], part);
             part = add_dpp<0xB1>(part);
             part = add_dpp<0x4E>(part);
             if (LPR >= 8) part = add_dpp<0x141>(part);
             if (LPR >= 16) part = add_dpp<0x140>(part);
             // the row's entry of A_t h is part 2^(n + eh); the bias joins it on that scale
-            float x = __builtin_fmaf(bcur[q].x, kHi, -(n + eh_f));
+            float x = __builtin_fmaf(bcur[q].x, kHi, -(nrow[q] + eh_f));
             x = __builtin_fmaf(bcur[q].x, kLo, x);
             val[q] = part;
-            nrow[q] = n;
             barg[q] = x;
             bmax = C::max_(bmax, x);
         }
@@ -142,7 +162,7 @@ template <int DP> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk
         for (int q = 0; q < Q; ++q) {
             const float bv = C::apply_sign(__builtin_amdgcn_exp2f(barg[q] - down), bcur[q].y);
             val[q] = __builtin_ldexpf(val[q], idown) + bv;
-            if (row_owner) {
+            if (out0 && row_owner) {
                 const float re = C::out_re_f(val[q], nrow[q] + ecur_f);
                 const float im = val[q] < 0.0f ? C::pi() : 0.0f;
                 *reinterpret_cast<float2 *>(out0 + ((size_t)t * DP + q * RPP + rsub) * 2) = float2{re, im};
@@ -176,19 +196,62 @@ template <int DP> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            cur[q] = nxt[q];
+            if (!TI) cur[q] = nxt[q];
             bcur[q] = bnxt[q];
+        }
+    }
+
+    if (a.out_fact_final) {
+        // the chunk's vector as column bias_col of the chunk's factored total, with its own exponent
+        unsigned char *dst = a.out_fact_final + (item * a.chunks_per_item + chunk) * a.fact_stride;
+        float *mp = reinterpret_cast<float *>(dst);
+        double *ep = reinterpret_cast<double *>(dst + (size_t)DP * a.fact_cols * sizeof(float));
+        if (rsub == 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mp[(size_t)(c4 + e) * a.fact_cols + a.bias_col] = hm[e];
+        }
+        if (lane == 0) ep[a.bias_col] = eh;
+    }
+}
+
+// Time-invariant recurrence: every chunk's total is [A^L | b*_c].  A^L has been written to the first
+// chunk's slot of each batch item; this copies it to the other chunks and clears the padding columns
+// (column d, the bias, is written by the walk kernel).
+__global__ __launch_bounds__(256) void replicate_power_kernel(unsigned char *totals, long long stride, int fact_cols, int dp, int d,
+                                                              long long chunks, long long chunks_per_item)
+{
+    const long long item = blockIdx.x / chunks, chunk = blockIdx.x % chunks;
+    const unsigned char *src = totals + (item * chunks_per_item) * stride;
+    unsigned char *dst = totals + (item * chunks_per_item + chunk) * stride;
+    const float *sm = reinterpret_cast<const float *>(src);
+    float *dm = reinterpret_cast<float *>(dst);
+    const size_t mant = (size_t)dp * fact_cols * sizeof(float);
+    const double *se = reinterpret_cast<const double *>(src + mant);
+    double *de = reinterpret_cast<double *>(dst + mant);
+    for (int e = threadIdx.x; e < dp * fact_cols; e += 256) {
+        const int col = e % fact_cols;
+        if (col < d) {
+            if (chunk != 0) dm[e] = sm[e];
+        } else if (col > d) {
+            dm[e] = 0.0f;
+        }
+    }
+    for (int col = threadIdx.x; col < fact_cols; col += 256) {
+        if (col < d) {
+            if (chunk != 0) de[col] = se[col];
+        } else if (col > d) {
+            de[col] = 0.0;
         }
     }
 }
 
-template <int DP> int launch_walk(goom_ctx *ctx, const ChainArgs &args, long long nchains, const char *label)
+template <int DP, bool TI> int launch_walk(goom_ctx *ctx, const ChainArgs &args, long long nchains, const char *label)
 {
     const long long grid = (nchains + kWalkWaves - 1) / kWalkWaves;
     if (grid <= 0) return GOOM_OK;
     if (grid > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many chains for one launch (%lld)", nchains);
     goom::prof_begin(ctx, label);
-    hipLaunchKernelGGL(affine_walk_kernel<DP>, dim3((unsigned)grid), dim3(kWalkWaves * 64), 0, ctx->stream, args, nchains);
+    hipLaunchKernelGGL((affine_walk_kernel<DP, TI>), dim3((unsigned)grid), dim3(kWalkWaves * 64), 0, ctx->stream, args, nchains);
     goom::prof_end(ctx);
     return goom::check_hip(ctx, hipGetLastError(), "launch affine_walk_kernel");
 }
@@ -213,18 +276,31 @@ int dispatch_affine_chunk(goom_ctx *ctx, const ChainArgs &args, int dp, long lon
     }
 }
 
-// the walk: a single state column that receives the bias, started from factored carries,
-// every state stored as GOOMs
+// the walk: a single state column that receives the bias, started from factored carries (or from
+// zero), every state stored as GOOMs and / or the last one as a column of the chunk's factored total
 bool affine_walk_applies(const ChainArgs &args, int dp)
 {
-    return (dp == 16 || dp == 32) && args.n == dp && args.d == dp && args.m == 1 && args.bias_mode == 1 && args.bias_col == 0 &&
-           args.init_mode == 1 && args.out_goom != nullptr && !args.out_goom_last_only && args.out_fact_steps == nullptr &&
-           args.out_fact_final == nullptr;
+    return (dp == 16 || dp == 32) && args.n == dp && args.d == dp && args.m == 1 && args.bias_mode == 1 &&
+           (args.init_mode == 1 || args.init_mode == 3) && (args.out_goom != nullptr || args.out_fact_final != nullptr) &&
+           !args.out_goom_last_only && args.out_fact_steps == nullptr && (args.out_goom == nullptr || args.bias_col == 0);
 }
 
 int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long nchains, const char *label)
 {
-    return dp == 16 ? launch_walk<16>(ctx, args, nchains, label) : launch_walk<32>(ctx, args, nchains, label);
+    const bool ti = args.left_step_stride == 0;
+    if (dp == 16) return ti ? launch_walk<16, true>(ctx, args, nchains, label) : launch_walk<16, false>(ctx, args, nchains, label);
+    return ti ? launch_walk<32, true>(ctx, args, nchains, label) : launch_walk<32, false>(ctx, args, nchains, label);
+}
+
+int launch_replicate_power(goom_ctx *ctx, void *totals, long long stride, int fact_cols, int dp, int d, long long batch,
+                           long long chunks, long long chunks_per_item)
+{
+    const long long grid = batch * chunks;
+    if (grid <= 0) return GOOM_OK;
+    if (grid > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many chunks for one launch");
+    hipLaunchKernelGGL(replicate_power_kernel, dim3((unsigned)grid), dim3(256), 0, ctx->stream, static_cast<unsigned char *>(totals), stride,
+                       fact_cols, dp, d, chunks, chunks_per_item);
+    return goom::check_hip(ctx, hipGetLastError(), "launch replicate_power_kernel");
 }
 
 } // namespace goom_chain

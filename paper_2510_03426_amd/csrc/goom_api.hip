@@ -651,7 +651,10 @@ size_t goom_affine_scan_workspace_bytes(int64_t T, int d, int64_t batch, int dty
 int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H, int64_t T, int d,
                      int64_t batch, int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes)
 {
-    if (int s = check_scan_args(ctx, A, H, T, d, 1, batch, dtype, opts)) return s;
+    goom_scan_opts plain = opts ? *opts : goom_scan_opts{0, 0};
+    const bool ti = (plain.flags & GOOM_AFFINE_TIME_INVARIANT) != 0;
+    plain.flags &= ~GOOM_AFFINE_TIME_INVARIANT;
+    if (int s = check_scan_args(ctx, A, H, T, d, 1, batch, dtype, &plain)) return s;
     if (!bias) return fail(ctx, GOOM_EINVAL, "null data pointer");
     if (d >= GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "the recurrence with bias needs d < %d", GOOM_MAX_DIM);
     if (!aligned(bias, 16) || (h0 && !aligned(h0, 16))) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
@@ -667,8 +670,8 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
     base.d = d;
     base.batch = batch;
     base.left = A;
-    base.left_batch_stride = (long long)T * d * d * cb;
-    base.left_step_stride = (long long)d * d * cb;
+    base.left_batch_stride = ti ? (long long)d * d * cb : (long long)T * d * d * cb;
+    base.left_step_stride = ti ? 0 : (long long)d * d * cb; // a time-invariant matrix is every step's factor
     base.steps = T;
     base.bias_mode = 1;
     base.bias = bias;
@@ -690,7 +693,36 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
     unsigned char *carries = totals + p.tot_bytes;
     unsigned char *gtot = carries + p.car_bytes;
     unsigned char *gcar = gtot + p.gtot_bytes;
-    { // phase 1: augmented chunk products [A* | b*]
+    if (ti && dtype == GOOM_C64 && (d == 16 || d == 32)) {
+        // phase 1, time-invariant: every chunk's total is [A^L | b*_c].  A^L once per batch item (a chain
+        // of L equal factors), copied to all chunks; b*_c by a matrix-vector walk of the chunk from zero.
+        ChainLaunch l = base;
+        l.bias_mode = 0;
+        l.bias = nullptr;
+        l.m = d;
+        l.steps = p.L;
+        l.chunk_len = p.L;
+        l.chunks_launched = 1;
+        l.init_mode = 0;
+        l.out_fact_final = totals;
+        l.final_common_exponent = 1;
+        l.fact_stride = (long long)p.tot.stride * p.C;
+        l.fact_cols = p.tot.cols_padded;
+        l.label = "affine_phase1_matrix_power";
+        if (int s = launch_chain(ctx, l)) return s;
+        if (int s = goom_chain::launch_replicate_power(ctx, totals, (long long)p.tot.stride, p.tot.cols_padded, p.dp, d, batch, p.C - 1, p.C)) return s;
+        ChainLaunch w = base;
+        w.m = 1;
+        w.bias_col = d;
+        w.chunk_len = p.L;
+        w.chunks_launched = p.C - 1;
+        w.init_mode = 3;
+        w.out_fact_final = totals;
+        w.fact_stride = (long long)p.tot.stride;
+        w.fact_cols = p.tot.cols_padded;
+        w.label = "affine_phase1_chunk_vectors";
+        if (int s = launch_chain(ctx, w)) return s;
+    } else { // phase 1: augmented chunk products [A* | b*]
         ChainLaunch l = base;
         l.m = d + 1;
         l.bias_col = d;

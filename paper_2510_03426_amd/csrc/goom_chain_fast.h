@@ -393,6 +393,8 @@ bool affine_chunk_applies(const ChainArgs &args, int dp);
 int dispatch_affine_chunk(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label);
 bool affine_walk_applies(const ChainArgs &args, int dp);
 int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label);
+int launch_replicate_power(goom_ctx *ctx, void *totals, long long stride, int fact_cols, int dp, int d, long long batch,
+                           long long chunks, long long chunks_per_item);
 
 inline int dispatch_fast(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label)
 {

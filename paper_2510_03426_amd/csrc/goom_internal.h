@@ -121,3 +121,10 @@ int launch_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, s
 int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t nvec, int d, int dtype);
 
 } // namespace goom
+
+namespace goom_chain {
+// time-invariant recurrence: copy A^L from the first chunk's total of every batch item to the others
+int launch_replicate_power(goom_ctx *ctx, void *totals, long long stride, int fact_cols, int dp, int d, long long batch,
+                           long long chunks, long long chunks_per_item);
+} // namespace goom_chain
+
