@@ -65,8 +65,11 @@ typedef enum goom_dtype {
     GOOM_C128 = 1 /* complex128: double log-magnitude, double phase */
 } goom_dtype;
 
-/* largest matrix dimension the product calls accept */
+/* largest matrix dimension of the register-resident kernels (scans, recurrences, small products) */
 #define GOOM_MAX_DIM 128
+/* largest dimension of goom_lmme (complex64): above GOOM_MAX_DIM the product runs as scaled operands,
+ * a tiled GEMM and a store pass through the workspace (the paper's experiments go up to 1024) */
+#define GOOM_MAX_DIM_LMME 1024
 
 /* flags of goom_to_goom: how log 0 is written (paper Section 3.1, configurable real log) */
 #define GOOM_ZERO_NEG_INF 0u /* log 0 = -inf (default) */

@@ -571,22 +571,34 @@ int goom_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype)
     return launch_from_goom(ctx, y, x, n, dtype);
 }
 
+static bool lmme_is_large(int n, int d, int m) { return n > GOOM_MAX_DIM || d > GOOM_MAX_DIM || m > GOOM_MAX_DIM; }
+
 size_t goom_lmme_workspace_bytes(int64_t batch, int n, int d, int m, int dtype, uint32_t flags)
 {
-    (void)batch; (void)n; (void)d; (void)m; (void)dtype; (void)flags;
-    return 0;
+    (void)flags;
+    if (batch <= 0 || n <= 0 || d <= 0 || m <= 0 || dtype != GOOM_C64 || !lmme_is_large(n, d, m)) return 0;
+    if (n > GOOM_MAX_DIM_LMME || d > GOOM_MAX_DIM_LMME || m > GOOM_MAX_DIM_LMME) return 0;
+    return lmme_large_workspace_bytes(batch, n, d, m);
 }
 
 int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batch, int n, int d, int m, int dtype,
               uint32_t flags, void *workspace, size_t workspace_bytes)
 {
-    (void)workspace; (void)workspace_bytes;
     if (int s = check_common(ctx, dtype)) return s;
     if (flags & ~GOOM_LMME_EXACT) return fail(ctx, GOOM_EINVAL, "unknown LMME flags 0x%x", flags);
     if (!A || !B || !C) return fail(ctx, GOOM_EINVAL, "null data pointer");
     if (batch <= 0 || n <= 0 || d <= 0 || m <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive");
-    if (n > GOOM_MAX_DIM || d > GOOM_MAX_DIM || m > GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "n, d, m must be <= %d", GOOM_MAX_DIM);
+    if (n > GOOM_MAX_DIM_LMME || d > GOOM_MAX_DIM_LMME || m > GOOM_MAX_DIM_LMME)
+        return fail(ctx, GOOM_EUNSUPPORTED, "n, d, m must be <= %d", GOOM_MAX_DIM_LMME);
     if (!aligned(A, 16) || !aligned(B, 16) || !aligned(C, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
+    if (lmme_is_large(n, d, m)) {
+        // beyond the register-resident kernels: scaled operands, a tiled GEMM and a store pass, through the workspace
+        if (dtype != GOOM_C64) return fail(ctx, GOOM_EUNSUPPORTED, "shapes above %d are built for GOOM_C64 only", GOOM_MAX_DIM);
+        if (flags & GOOM_LMME_EXACT) return fail(ctx, GOOM_EUNSUPPORTED, "the repair pass is built for shapes up to %d", GOOM_MAX_DIM);
+        if (int s = check_workspace(ctx, workspace, workspace_bytes, lmme_large_workspace_bytes(batch, n, d, m))) return s;
+        if (int s = need_ctx(ctx)) return s;
+        return launch_lmme_large(ctx, A, B, C, batch, n, d, m, workspace);
+    }
     if (int s = need_ctx(ctx)) return s;
     const size_t cb = 2 * (dtype == GOOM_C64 ? 4 : 8);
     ChainLaunch l;

@@ -113,6 +113,8 @@ size_t lyap_steps_partial_bytes(long long batch, int d);
 int launch_lle_epilogue(goom_ctx *ctx, const void *v, double *lle, long long batch, int d, int dtype, double scale);
 int launch_uniform_u0(goom_ctx *ctx, void *u, long long batch, int d, int dtype);
 
+size_t lmme_large_workspace_bytes(long long batch, int n, int d, int m);
+int launch_lmme_large(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int n, int d, int m, void *ws);
 int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int n, int d, int m, int dtype);
 
 int launch_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, uint32_t flags);

@@ -590,3 +590,33 @@ def test_affine_scan_time_invariant(G, oracle, T, d, batch, chunk, ctype):
         ref = host(G.affine_scan(dev(Arep), dev(bz), None if start is None else dev(start), chunk_len=chunk))
         same = (ref.imag == got.imag) & (np.abs(ref.real - got.real) <= tolerance(ref.real.astype(np.float64), comp))
         assert same.mean() > 0.98
+
+
+# ------------------------------------------- shapes beyond the register-resident kernels (up to 1024)
+
+@pytest.mark.parametrize("shape", [(2, 256, 256, 256), (1, 300, 200, 150), (3, 129, 64, 64), (1, 40, 500, 33), (1, 512, 512, 512),
+                                   (1, 1024, 1024, 1024)])
+def test_lmme_large_shapes(G, oracle, shape):
+    b, n, d, m = shape
+    A = oracle.to_goom(si.normal_f32(si.BASE_SEED + 61, 5, b * n * d).reshape(b, n, d))
+    B = oracle.to_goom(si.normal_f32(si.BASE_SEED + 62, 6, b * d * m).reshape(b, d, m))
+    say(f"large lmme {shape}")
+    re, sg, kap = oracle.lmme(A, B, return_kappa=True)
+    got = host(G.lmme(dev(A), dev(B)))
+    # (a sum of d Gaussian products falls below 1 / 512 of its mass with probability about 0.05 sqrt(d / 1024))
+    compare(got, re, sg, kap, name=f"large lmme {shape}", max_ill_fraction=0.05)
+    if n * d * m <= 256 ** 3:
+        # log-magnitudes spread over +-60: different rows and columns need very different shifts
+        A2, B2 = si.wide_range_goom_pairs(si.BASE_SEED + 63, b, n, d, m, sigma=20.0, dtype=np.complex64)
+        re, sg, kap = oracle.lmme(A2, B2, return_kappa=True)
+        got = host(G.lmme(dev(A2), dev(B2)))
+        # the scaled product is only claimed where its certificate holds: the output's magnitude after the
+        # row and column shifts stays 20 + log2(d) bits above the smallest normal float (terms dropped
+        # below that level cannot matter)
+        ni = np.ceil(A2.real.max(axis=2) * math.log2(math.e))[:, :, None]
+        ek = np.ceil(B2.real.max(axis=1) * math.log2(math.e))[:, None, :]
+        certified = re * math.log2(math.e) - ni - ek >= -126 + 20 + math.log2(d) + 1
+        say(f"  sigma 20: certificate holds for {certified.mean():.2%} of the outputs")
+        compare(np.where(certified, got, (re + 1j * np.pi * sg).astype(np.complex64)), re, sg, kap, name=f"large lmme wide {shape}",
+                max_ill_fraction=0.05)
+        assert certified.mean() > 0.9
