@@ -140,12 +140,14 @@ static ScanPlan plan_scan(long long T, int d, int m_tot, int m_state, long long 
 }
 
 static int check_scan_args(goom_ctx *ctx, const void *M, const void *out, long long T, int d, int m, long long batch,
-                           int dtype, const goom_scan_opts *opts)
+                           int dtype, const goom_scan_opts *opts, int max_dim = GOOM_MAX_DIM)
 {
     if (int s = check_common(ctx, dtype)) return s;
     if (!M || !out) return fail(ctx, GOOM_EINVAL, "null data pointer");
     if (T <= 0 || batch <= 0 || d <= 0 || m <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive (T=%lld d=%d m=%d batch=%lld)", T, d, m, batch);
-    if (d > GOOM_MAX_DIM || m > GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "d and m must be <= %d (d=%d m=%d)", GOOM_MAX_DIM, d, m);
+    if (d > max_dim || m > max_dim) return fail(ctx, GOOM_EUNSUPPORTED, "d and m must be <= %d (d=%d m=%d)", max_dim, d, m);
+    if ((d > GOOM_MAX_DIM || m > GOOM_MAX_DIM) && dtype != GOOM_C64)
+        return fail(ctx, GOOM_EUNSUPPORTED, "matrices above %d are built for GOOM_C64 only", GOOM_MAX_DIM);
     if (opts && opts->flags != 0) return fail(ctx, GOOM_EINVAL, "unknown scan flags 0x%x", opts->flags);
     if (opts && opts->chunk_len < 0) return fail(ctx, GOOM_EINVAL, "negative chunk_len");
     if (!aligned(M, 16) || !aligned(out, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
@@ -275,9 +277,16 @@ static int carry_phase(goom_ctx *ctx, const ScanPlan &p, int dtype, int d, long 
 static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, long long T, int d, int m, long long batch,
                     int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes, bool final_only)
 {
-    if (int s = check_scan_args(ctx, M, P, T, d, m, batch, dtype, opts)) return s;
+    if (int s = check_scan_args(ctx, M, P, T, d, m, batch, dtype, opts, GOOM_MAX_DIM_LMME)) return s;
     if (!init && m != d) return fail(ctx, GOOM_EINVAL, "without an initial state the outputs are d x d (m=%d d=%d)", m, d);
     if (init && !aligned(init, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
+    if (d > GOOM_MAX_DIM || m > GOOM_MAX_DIM) {
+        // the state no longer fits a workgroup: chains advance step by step through a tiled GEMM
+        const long long req = opts ? opts->chunk_len : 0;
+        if (int s = check_workspace(ctx, ws, ws_bytes, scan_large_workspace_bytes(T, d, m, batch, req, final_only))) return s;
+        if (int s = need_ctx(ctx)) return s;
+        return run_scan_large(ctx, M, init, P, T, d, m, batch, req, ws, final_only);
+    }
     const ScanPlan p = plan_scan(T, d, d, m, batch, dtype, opts ? opts->chunk_len : 0, final_only);
     if (int s = check_workspace(ctx, ws, ws_bytes, p.total())) return s;
     const size_t cb = 2 * comp_bytes(dtype);
@@ -626,16 +635,20 @@ int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batc
 
 size_t goom_scan_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype, const goom_scan_opts *opts)
 {
-    if (T <= 0 || d <= 0 || m <= 0 || batch <= 0 || d > GOOM_MAX_DIM || m > GOOM_MAX_DIM) return 0;
+    if (T <= 0 || d <= 0 || m <= 0 || batch <= 0 || d > GOOM_MAX_DIM_LMME || m > GOOM_MAX_DIM_LMME) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
+    if (d > GOOM_MAX_DIM || m > GOOM_MAX_DIM)
+        return dtype == GOOM_C64 ? scan_large_workspace_bytes(T, d, m, batch, opts ? opts->chunk_len : 0, false) : 0;
     ScanPlan p = plan_scan(T, d, d, m, batch, dtype, opts ? opts->chunk_len : 0, false);
     return p.total();
 }
 
 size_t goom_reduce_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype, const goom_scan_opts *opts)
 {
-    if (T <= 0 || d <= 0 || m <= 0 || batch <= 0 || d > GOOM_MAX_DIM || m > GOOM_MAX_DIM) return 0;
+    if (T <= 0 || d <= 0 || m <= 0 || batch <= 0 || d > GOOM_MAX_DIM_LMME || m > GOOM_MAX_DIM_LMME) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
+    if (d > GOOM_MAX_DIM || m > GOOM_MAX_DIM)
+        return dtype == GOOM_C64 ? scan_large_workspace_bytes(T, d, m, batch, opts ? opts->chunk_len : 0, true) : 0;
     ScanPlan p = plan_scan(T, d, d, m, batch, dtype, opts ? opts->chunk_len : 0, true);
     return p.total();
 }

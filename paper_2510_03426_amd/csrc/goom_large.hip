@@ -10,6 +10,8 @@
 //   4. signed logarithm, shifts re-added, transposed back on the way out.
 // All intermediates live in the caller's workspace, padded to the tile sizes, so the GEMM has no
 // edge cases.
+#include <cmath>
+
 #include "goom_chain_kernel.h"
 
 namespace {
@@ -61,7 +63,8 @@ __global__ __launch_bounds__(256) void convert_left_kernel(const float2 *__restr
 }
 
 // ---- 2a. column maxima of the right operand.  grid (ceil(m / 64), batch), block 64 x 4.
-__global__ __launch_bounds__(256) void column_shift_kernel(const float2 *__restrict__ B, float *__restrict__ shifts, int d, int m, int cols_padded)
+template <typename S>
+__global__ __launch_bounds__(256) void column_shift_kernel(const float2 *__restrict__ B, S *__restrict__ shifts, int d, int m, int cols_padded)
 {
     __shared__ float red[4][64];
     const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
@@ -74,13 +77,14 @@ __global__ __launch_bounds__(256) void column_shift_kernel(const float2 *__restr
     __syncthreads();
     if (ry == 0 && col < cols_padded) {
         mx = fmaxf(fmaxf(red[0][cx], red[1][cx]), fmaxf(red[2][cx], red[3][cx]));
-        shifts[(size_t)b * cols_padded + col] = (col < m && mx > -__builtin_huge_valf()) ? ceilf(mx * kLog2eF) : 0.0f;
+        shifts[(size_t)b * cols_padded + col] = (col < m && mx > -__builtin_huge_valf()) ? (S)ceilf(mx * kLog2eF) : (S)0;
     }
 }
 
 // ---- 2b. right operand scaled and transposed: Y[b][col][j] = (+-) 2^(log2|B_j,col| - shift_col).
 // grid (cols_padded / 32, k_padded / 32 rounded up, batch), block 32 x 8.
-__global__ __launch_bounds__(256) void convert_right_kernel(const float2 *__restrict__ B, const float *__restrict__ shifts, float *__restrict__ Y,
+template <typename S>
+__global__ __launch_bounds__(256) void convert_right_kernel(const float2 *__restrict__ B, const S *__restrict__ shifts, float *__restrict__ Y,
                                                             int d, int m, int cols_padded, int k_padded)
 {
     __shared__ float tile[32][33];
@@ -88,7 +92,7 @@ __global__ __launch_bounds__(256) void convert_right_kernel(const float2 *__rest
     const int c0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
     const long long b = blockIdx.z;
     const int col = c0 + tx;
-    const float sh = col < cols_padded ? shifts[(size_t)b * cols_padded + col] : 0.0f;
+    const float sh = col < cols_padded ? (float)shifts[(size_t)b * cols_padded + col] : 0.0f;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int j = j0 + ty + 8 * r;
@@ -204,6 +208,170 @@ __global__ __launch_bounds__(256) void lmme_store_kernel(const float *__restrict
     }
 }
 
+
+// =====================================================================================
+// Scans of matrices above 128 x 128 (paper Section 4.1 runs chains up to 1024 x 1024).  The running
+// product of a chain is kept TRANSPOSED, St[column of the state][row], as float mantissas with one
+// power-of-two exponent per state column (double), so that one step,
+//     St <- St A~^T,  then every row of St rescaled (the row shifts of A~ folded in),
+// is the same NT GEMM plus two light passes, and closes under iteration.  All chains of a launch
+// (batch items x chunks) advance together, one step per round of launches.
+// =====================================================================================
+
+struct ChainGeom {
+    long long T, L;           // chain length, chunk length
+    long long chunks;         // chunks per batch item the launch covers (chain = item * chunks + chunk)
+    int d, dp;                // matrix size, padded to 128
+};
+
+// rows of M[b][chunk * L + s], scaled; a chain whose chunk has fewer than s + 1 steps gets the identity.
+// grid (dp, chains), 256 threads.
+__global__ __launch_bounds__(256) void chain_convert_left_kernel(const float2 *__restrict__ M, float *__restrict__ X, double *__restrict__ shifts,
+                                                                 ChainGeom q, long long s)
+{
+    __shared__ float red[4];
+    const int row = blockIdx.x, tid = threadIdx.x;
+    const long long chain = blockIdx.y, item = chain / q.chunks, chunk = chain % q.chunks;
+    const long long t = chunk * q.L + s;
+    const bool active = s < q.L && t < q.T;
+    float *xrow = X + ((size_t)chain * q.dp + row) * q.dp;
+    if (!active || row >= q.d) {
+        for (int j = tid; j < q.dp; j += 256) xrow[j] = (!active && j == row && row < q.d) ? 1.0f : 0.0f;
+        if (tid == 0) shifts[(size_t)chain * q.dp + row] = 0.0;
+        return;
+    }
+    const float2 *arow = M + (((size_t)item * q.T + t) * q.d + row) * q.d;
+    float mx = -__builtin_huge_valf();
+    for (int j = tid; j < q.d; j += 256) mx = fmaxf(mx, arow[j].x);
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) mx = fmaxf(mx, __shfl_xor(mx, sft, 64));
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const bool zero_row = !(mx > -__builtin_huge_valf());
+    const float sh = zero_row ? 0.0f : ceilf(mx * kLog2eF);
+    for (int j = tid; j < q.dp; j += 256) {
+        float v = 0.0f;
+        if (j < q.d && !zero_row) {
+            const float2 e = arow[j];
+            v = signed_scaled(e.x, e.y, sh);
+        }
+        xrow[j] = v;
+    }
+    if (tid == 0) shifts[(size_t)chain * q.dp + row] = (double)sh;
+}
+
+// Row n of the product (state column n): out[n][i] = in[n][i] 2^(shift_i - s_n) with s_n the largest
+// exponent of in[n][i] 2^shift_i, and the column's exponent grows by s_n.  shifts: [.][len] doubles with
+// stride shift_stride per chain (0: the same vector for all), or NULL for none.
+// grid (rows, chains), 256 threads; in and out may be the same buffer.
+__global__ __launch_bounds__(256) void rescale_rows_kernel(const float *in, float *out, const double *__restrict__ shifts, long long shift_stride,
+                                                           double *__restrict__ expo, int rows_padded, int len)
+{
+    __shared__ float red[4];
+    const int n = blockIdx.x, tid = threadIdx.x;
+    const long long chain = blockIdx.y;
+    const float *src = in + ((size_t)chain * rows_padded + n) * len;
+    float *dst = out + ((size_t)chain * rows_padded + n) * len;
+    const double *sh = shifts ? shifts + (size_t)chain * shift_stride : nullptr;
+    // shifts relative to their largest, so that they fit float arithmetic next to the entries' exponents
+    float v[4], rel[4];
+    double smax = -1.0e300;
+    if (sh)
+        for (int i = tid; i < len; i += 256) smax = fmax(smax, sh[i]);
+    else
+        smax = 0.0;
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) smax = fmax(smax, __shfl_xor(smax, sft, 64));
+    __shared__ double dred[4];
+    if ((tid & 63) == 0) dred[tid >> 6] = smax;
+    __syncthreads();
+    smax = fmax(fmax(dred[0], dred[1]), fmax(dred[2], dred[3]));
+    float mx = -1.0e30f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = tid + 256 * r;
+        v[r] = 0.0f;
+        rel[r] = 0.0f;
+        if (i < len) {
+            v[r] = src[i];
+            const double dr = sh ? sh[i] - smax : 0.0;
+            rel[r] = dr > -4000.0 ? (float)dr : -4000.0f;
+            if (v[r] != 0.0f) mx = fmaxf(mx, CF::exponent_of(v[r]) + rel[r]);
+        }
+    }
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) mx = fmaxf(mx, __shfl_xor(mx, sft, 64));
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const bool all_zero = !(mx > -1.0e29f);
+    const float sn = all_zero ? 0.0f : mx;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = tid + 256 * r;
+        if (i < len) dst[i] = __builtin_ldexpf(v[r], (int)CF::clamp_shift(rel[r] - sn));
+    }
+    if (tid == 0) {
+        double &e = expo[(size_t)chain * rows_padded + n];
+        e = all_zero ? 0.0 : e + smax + (double)sn;
+    }
+}
+
+// St = identity (first d rows and columns), exponents 0.  grid (rows_padded, chains), 256 threads.
+__global__ __launch_bounds__(256) void state_identity_kernel(float *St, double *expo, int rows_padded, int len, int d)
+{
+    const int n = blockIdx.x;
+    const long long chain = blockIdx.y;
+    float *row = St + ((size_t)chain * rows_padded + n) * len;
+    for (int i = threadIdx.x; i < len; i += 256) row[i] = (i == n && n < d) ? 1.0f : 0.0f;
+    if (threadIdx.x == 0) expo[(size_t)chain * rows_padded + n] = 0.0;
+}
+
+// out[b][j][i] = in[b][i][j], square dp x dp.  grid (dp / 32, dp / 32, batch), block 32 x 8.
+__global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ in, long long in_stride, float *__restrict__ out, long long out_stride,
+                                                        int dp)
+{
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int i0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
+    const long long b = blockIdx.z;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) tile[ty + 8 * r][tx] = in[b * in_stride + (size_t)(i0 + ty + 8 * r) * dp + j0 + tx];
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) out[b * out_stride + (size_t)(j0 + ty + 8 * r) * dp + i0 + tx] = tile[tx][ty + 8 * r];
+}
+
+// P[b][t][i][n] = GOOM of St[chain][n][i] 2^(expo[chain][n]), t = chunk * L + s (or slot `fixed_slot`
+// of a [b][slots] array when fixed_slot >= 0); chains without that step store nothing.
+// grid (ceil(d / 32), ceil(m / 32), chains), block 32 x 8.
+__global__ __launch_bounds__(256) void chain_store_kernel(const float *__restrict__ St, const double *__restrict__ expo, float2 *__restrict__ P,
+                                                          ChainGeom q, long long s, int m, int rows_padded, long long slots, long long fixed_slot)
+{
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int i0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
+    const long long chain = blockIdx.z, item = chain / q.chunks, chunk = chain % q.chunks;
+    const long long t = chunk * q.L + s;
+    if (fixed_slot < 0 && !(s < q.L && t < q.T)) return;
+    const long long slot = fixed_slot >= 0 ? fixed_slot : t;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) tile[ty + 8 * r][tx] = St[((size_t)chain * rows_padded + n0 + ty + 8 * r) * q.dp + i0 + tx]; // [n][i]
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = i0 + ty + 8 * r, n = n0 + tx;
+        if (i < q.d && n < m) {
+            const float x = tile[tx][ty + 8 * r];
+            float2 o;
+            o.x = x != 0.0f ? CF::out_re((float)x, 0.0f, expo[(size_t)chain * rows_padded + n]) : -__builtin_huge_valf();
+            o.y = x < 0.0f ? CF::pi() : 0.0f;
+            P[(((size_t)item * slots + slot) * q.d + i) * m + n] = o;
+        }
+    }
+}
+
 inline int pad_to(int v, int a) { return (v + a - 1) / a * a; }
 
 } // namespace
@@ -235,8 +403,8 @@ int launch_lmme_large(goom_ctx *ctx, const void *A, const void *B, void *C, long
     const unsigned nb = (unsigned)batch;
     prof_begin(ctx, "lmme_large_scale_operands");
     hipLaunchKernelGGL(convert_left_kernel, dim3(Np, nb), dim3(256), 0, ctx->stream, static_cast<const float2 *>(A), X, rs, n, d, Np, Kp);
-    hipLaunchKernelGGL(column_shift_kernel, dim3(Mp / 64, nb), dim3(256), 0, ctx->stream, static_cast<const float2 *>(B), cs, d, m, Mp);
-    hipLaunchKernelGGL(convert_right_kernel, dim3(Mp / 32, (Kp + 31) / 32, nb), dim3(256), 0, ctx->stream, static_cast<const float2 *>(B), cs, Y,
+    hipLaunchKernelGGL(column_shift_kernel<float>, dim3(Mp / 64, nb), dim3(256), 0, ctx->stream, static_cast<const float2 *>(B), cs, d, m, Mp);
+    hipLaunchKernelGGL(convert_right_kernel<float>, dim3(Mp / 32, (Kp + 31) / 32, nb), dim3(256), 0, ctx->stream, static_cast<const float2 *>(B), cs, Y,
                        d, m, Mp, Kp);
     prof_end(ctx);
     if (int s = check_hip(ctx, hipGetLastError(), "launch LMME operand kernels")) return s;
@@ -250,6 +418,175 @@ int launch_lmme_large(goom_ctx *ctx, const void *A, const void *B, void *C, long
                        static_cast<float2 *>(C), n, m, Np, Mp);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch lmme_store_kernel");
+}
+
+} // namespace goom
+
+// ------------------------------------------------------------------------------------------------
+// Scan / reduction driver for matrices above 128 x 128: the three phases of the chunked scan, every
+// phase advancing all of its chains by one step per round of launches.
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+struct LargePlan {
+    long long L, C, C1; // chunk length, chunks per item, chunks whose products phase 1 forms
+    int dp, mp;
+    size_t off_atil, off_na, off_s1, off_e1, off_s3, off_e3, off_cbuf, off_yt, off_ey, off_trow, total;
+};
+
+LargePlan plan_large(long long T, int d, int m, long long batch, long long requested, bool final_only)
+{
+    LargePlan p;
+    p.dp = pad_to(d, 128);
+    p.mp = pad_to(m, 128);
+    const long long tiles = (long long)(p.dp / 128) * (p.dp / 128);
+    const size_t per_chain = ((size_t)3 * p.dp * p.dp + (size_t)2 * p.mp * p.dp) * 4;
+    long long c;
+    if (requested > 0) {
+        c = (T + requested - 1) / requested;
+    } else {
+        const long long c_par = (512 + batch * tiles - 1) / (batch * tiles); // enough tiles to fill the chip
+        const long long c_depth = (long long)std::ceil(std::sqrt(2.0 * (double)T));
+        c = c_par < c_depth ? c_par : c_depth;
+        const long long c_mem = (long long)((size_t)8 << 30) / (long long)(per_chain * (size_t)batch);
+        if (c > c_mem) c = c_mem;
+    }
+    if (c < 1) c = 1;
+    p.L = (T + c - 1) / c;
+    p.C = (T + p.L - 1) / p.L;
+    p.C1 = p.C <= 1 ? 0 : (final_only ? p.C : p.C - 1);
+    const size_t chains = (size_t)batch * p.C;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += goom::align_up(bytes, 256); return o; };
+    p.off_atil = take(chains * p.dp * p.dp * 4);
+    p.off_na = take(chains * p.dp * 8);
+    p.off_s1 = take((size_t)batch * p.C1 * p.dp * p.dp * 4);
+    p.off_e1 = take((size_t)batch * p.C1 * p.dp * 8);
+    p.off_s3 = take(final_only ? 0 : chains * p.mp * p.dp * 4);
+    p.off_e3 = take(final_only ? 0 : chains * p.mp * 8);
+    p.off_cbuf = take(chains * (size_t)(p.mp > p.dp ? p.mp : p.dp) * p.dp * 4);
+    p.off_yt = take((size_t)batch * p.mp * p.dp * 4);
+    p.off_ey = take((size_t)batch * p.mp * 8);
+    p.off_trow = take((size_t)batch * p.dp * p.dp * 4);
+    p.total = off;
+    return p;
+}
+
+// copies batch states (rows x len floats and rows doubles each) between strided arrays
+__global__ __launch_bounds__(256) void copy_state_kernel(const float *src, long long src_stride, const double *esrc, long long esrc_stride, float *dst,
+                                                         long long dst_stride, double *edst, long long edst_stride, int rows, int len)
+{
+    const long long b = blockIdx.y;
+    const int n = blockIdx.x;
+    const float *s = src + b * src_stride + (size_t)n * len;
+    float *t = dst + b * dst_stride + (size_t)n * len;
+    for (int i = threadIdx.x; i < len; i += 256) t[i] = s[i];
+    if (threadIdx.x == 0) edst[b * edst_stride + n] = esrc[b * esrc_stride + n];
+}
+
+} // namespace
+
+namespace goom {
+
+size_t scan_large_workspace_bytes(long long T, int d, int m, long long batch, long long requested_chunk, bool final_only)
+{
+    return plan_large(T, d, m, batch, requested_chunk, final_only).total;
+}
+
+int run_scan_large(goom_ctx *ctx, const void *M, const void *init, void *P, long long T, int d, int m, long long batch,
+                   long long requested_chunk, void *ws, bool final_only)
+{
+    const LargePlan p = plan_large(T, d, m, batch, requested_chunk, final_only);
+    const long long chains_all = batch * p.C;
+    if (chains_all > 65535) return fail(ctx, GOOM_EUNSUPPORTED, "too many chains (%lld) for matrices above %d", chains_all, GOOM_MAX_DIM);
+    unsigned char *w = static_cast<unsigned char *>(ws);
+    float *atil = reinterpret_cast<float *>(w + p.off_atil);
+    double *na = reinterpret_cast<double *>(w + p.off_na);
+    float *s1 = reinterpret_cast<float *>(w + p.off_s1);
+    double *e1 = reinterpret_cast<double *>(w + p.off_e1);
+    float *s3 = reinterpret_cast<float *>(w + p.off_s3);
+    double *e3 = reinterpret_cast<double *>(w + p.off_e3);
+    float *cbuf = reinterpret_cast<float *>(w + p.off_cbuf);
+    float *yt = reinterpret_cast<float *>(w + p.off_yt);
+    double *ey = reinterpret_cast<double *>(w + p.off_ey);
+    float *trow = reinterpret_cast<float *>(w + p.off_trow);
+    const float2 *Mg = static_cast<const float2 *>(M);
+    const int dp = p.dp, mp = p.mp;
+    hipStream_t st = ctx->stream;
+    auto ok = [&](const char *what) { return check_hip(ctx, hipGetLastError(), what); };
+
+    // one step of all chains of a launch: state[chain] (rows x dp) <- state A~^T, rescaled
+    auto advance = [&](float *state, double *expo, int rows, const ChainGeom &q, long long chains, long long s) {
+        hipLaunchKernelGGL(chain_convert_left_kernel, dim3(dp, (unsigned)chains), dim3(256), 0, st, Mg, atil, na, q, s);
+        hipLaunchKernelGGL(gemm_nt_kernel, dim3(dp / BN, rows / BM, (unsigned)chains), dim3(256), 0, st, state, atil, cbuf, rows, dp, dp,
+                           (long long)rows * dp, (long long)dp * dp, (long long)rows * dp);
+        hipLaunchKernelGGL(rescale_rows_kernel, dim3(rows, (unsigned)chains), dim3(256), 0, st, cbuf, state, na, (long long)dp, expo, rows, dp);
+    };
+
+    // ---- phase 1: chunk products
+    if (p.C1 > 0) {
+        ChainGeom q{T, p.L, p.C1, d, dp};
+        const long long chains = batch * p.C1;
+        prof_begin(ctx, "scan_large_phase1_chunk_products");
+        hipLaunchKernelGGL(state_identity_kernel, dim3(dp, (unsigned)chains), dim3(256), 0, st, s1, e1, dp, dp, d);
+        for (long long s = 0; s < p.L; ++s) advance(s1, e1, dp, q, chains, s);
+        prof_end(ctx);
+        if (int e = ok("scan_large phase 1")) return e;
+    }
+
+    // ---- phase 2: prefixes at the chunk boundaries (and, for a reduction, the final product)
+    prof_begin(ctx, "scan_large_phase2_carries");
+    if (init) {
+        hipLaunchKernelGGL(column_shift_kernel<double>, dim3(mp / 64, (unsigned)batch), dim3(256), 0, st, static_cast<const float2 *>(init), ey, d, m, mp);
+        hipLaunchKernelGGL(convert_right_kernel<double>, dim3(mp / 32, dp / 32, (unsigned)batch), dim3(256), 0, st, static_cast<const float2 *>(init),
+                           ey, yt, d, m, mp, dp);
+    } else {
+        hipLaunchKernelGGL(state_identity_kernel, dim3(mp, (unsigned)batch), dim3(256), 0, st, yt, ey, mp, dp, d);
+    }
+    for (long long c = 0; c < p.C; ++c) {
+        if (!final_only)
+            hipLaunchKernelGGL(copy_state_kernel, dim3(mp, (unsigned)batch), dim3(256), 0, st, yt, (long long)mp * dp, ey, (long long)mp,
+                               s3 + (size_t)c * mp * dp, (long long)p.C * mp * dp, e3 + (size_t)c * mp, (long long)p.C * mp, mp, dp);
+        if (c < p.C1) {
+            // Y <- T_c Y: the exponents of T_c's columns go onto Y's rows, T_c is turned K-contiguous
+            hipLaunchKernelGGL(rescale_rows_kernel, dim3(mp, (unsigned)batch), dim3(256), 0, st, yt, yt, e1 + (size_t)c * dp, (long long)p.C1 * dp, ey,
+                               mp, dp);
+            hipLaunchKernelGGL(transpose_kernel, dim3(dp / 32, dp / 32, (unsigned)batch), dim3(256), 0, st, s1 + (size_t)c * dp * dp,
+                               (long long)p.C1 * dp * dp, trow, (long long)dp * dp, dp);
+            hipLaunchKernelGGL(gemm_nt_kernel, dim3(dp / BN, mp / BM, (unsigned)batch), dim3(256), 0, st, yt, trow, cbuf, mp, dp, dp, (long long)mp * dp,
+                               (long long)dp * dp, (long long)mp * dp);
+            hipLaunchKernelGGL(rescale_rows_kernel, dim3(mp, (unsigned)batch), dim3(256), 0, st, cbuf, yt, (const double *)nullptr, 0LL, ey, mp, dp);
+        }
+    }
+    if (final_only && p.C1 > 0) {
+        ChainGeom q{T, p.L, 1, d, dp};
+        hipLaunchKernelGGL(chain_store_kernel, dim3((d + 31) / 32, (m + 31) / 32, (unsigned)batch), dim3(256), 0, st, yt, ey, static_cast<float2 *>(P), q,
+                           0LL, m, mp, 1LL, 0LL);
+    }
+    prof_end(ctx);
+    if (int e = ok("scan_large phase 2")) return e;
+    if (final_only && p.C1 > 0) return GOOM_OK;
+
+    // ---- phase 3: every chunk from its incoming prefix, all prefixes stored (a single chunk runs only this)
+    {
+        ChainGeom q{T, p.L, p.C, d, dp};
+        float *state = final_only ? yt : s3; // a reduction of a single chunk walks it here
+        double *expo = final_only ? ey : e3;
+        prof_begin(ctx, final_only ? "scan_large_single_chunk" : "scan_large_phase3_outputs");
+        for (long long s = 0; s < p.L; ++s) {
+            advance(state, expo, mp, q, chains_all, s);
+            if (!final_only)
+                hipLaunchKernelGGL(chain_store_kernel, dim3((d + 31) / 32, (m + 31) / 32, (unsigned)chains_all), dim3(256), 0, st, state, expo,
+                                   static_cast<float2 *>(P), q, s, m, mp, T, -1LL);
+        }
+        if (final_only) {
+            ChainGeom q1{T, p.L, 1, d, dp};
+            hipLaunchKernelGGL(chain_store_kernel, dim3((d + 31) / 32, (m + 31) / 32, (unsigned)batch), dim3(256), 0, st, state, expo,
+                               static_cast<float2 *>(P), q1, 0LL, m, mp, 1LL, 0LL);
+        }
+        prof_end(ctx);
+    }
+    return ok("scan_large phase 3");
 }
 
 } // namespace goom

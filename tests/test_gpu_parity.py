@@ -620,3 +620,24 @@ def test_lmme_large_shapes(G, oracle, shape):
         compare(np.where(certified, got, (re + 1j * np.pi * sg).astype(np.complex64)), re, sg, kap, name=f"large lmme wide {shape}",
                 max_ill_fraction=0.05)
         assert certified.mean() > 0.9
+
+
+@pytest.mark.parametrize("T,d,chunk,m,batch", [(24, 256, 0, None, 1), (10, 200, 3, None, 2), (9, 160, 4, 70, 1), (6, 512, 2, None, 1),
+                                               (5, 300, 5, 300, 1), (3, 1024, 0, None, 1)])
+def test_scan_large_matrices(G, oracle, T, d, chunk, m, batch):
+    say(f"large scan T={T} d={d} chunk={chunk} m={m} batch={batch}")
+    for b in range(batch):
+        pass
+    Z = oracle.to_goom(si.normal_f32(si.BASE_SEED + 64, 12, batch * T * d * d).reshape(batch, T, d, d))
+    init = None
+    if m is not None:
+        init = oracle.to_goom(si.normal_f32(si.BASE_SEED + 65, 13, batch * d * m).reshape(batch, d, m))
+    out = host(G.scan(dev(Z), None if init is None else dev(init), chunk_len=chunk))
+    fin = host(G.reduce(dev(Z), None if init is None else dev(init), chunk_len=chunk))
+    mm = d if m is None else m
+    sample = sorted({0, 1, T // 2, T - 1})
+    for b in range(batch):
+        st = oracle.ScanStream(d, m=mm, init=None if init is None else init[b], scaled=True)
+        re, sg, kap = st.advance(Z[b], sample_t=sample, return_kappa=True)
+        compare(out[b][sample], re, sg, kap, name=f"large scan T{T}d{d} item {b}", max_ill_fraction=0.06)
+        compare(fin[b], re[-1], sg[-1], kap[-1], name=f"large reduce T{T}d{d} item {b}", max_ill_fraction=0.06)
