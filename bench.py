@@ -32,7 +32,7 @@ def main():
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs")
     ap.add_argument("--no-extras", action="store_true", help="time the headline scan only")
-    ap.add_argument("--only", choices=["tiny", "scan128", "lmme", "lyapunov", "recurrence"], default=None,
+    ap.add_argument("--only", choices=["tiny", "scan128", "lmme", "lyapunov", "recurrence", "large"], default=None,
                     help="time just one of the other workloads (for profiler runs) and print its figures")
     ap.add_argument("--basic-extras", action="store_true",
                     help="besides the scan, time only a plain device copy of the same size (for counter runs)")
@@ -237,6 +237,8 @@ def other_workloads(g, torch, dev, only=None):
         res.update(lyapunov(g, torch, dev, si))
     if want("recurrence"):
         res.update(recurrence(g, torch, dev, si))
+    if want("large"):
+        res.update(large_matrices(g, torch, dev, si))
     return res
 
 
@@ -323,6 +325,36 @@ def lyapunov(g, torch, dev, si):
         "ms": round(sec * 1e3, 3), "jacobians_per_s": round(T / sec, 1),
         "kernels_ms": kernel_times(g, lambda: g.scan_reset(Jz))}
     del Jz
+    return res
+
+
+def large_matrices(g, torch, dev, si):
+    # matrices beyond the register-resident kernels: LMME of 32 pairs of 1024 x 1024, scans of 1024 x 1024
+    # (T = 512) and 256 x 256 (T = 32,768) matrices with N(0,1) entries
+    res = {}
+    B, n = 32, 1024
+    a = g.to_goom(torch.randn((B, n, n), device=dev, generator=si.device_generator(251003426 * 10 + 71, dev)))
+    b = g.to_goom(torch.randn((B, n, n), device=dev, generator=si.device_generator(251003426 * 10 + 72, dev)))
+    c = torch.empty_like(a)
+    sec = timed(torch, lambda: g.lmme(a, b, out=c), 5)
+    kt = kernel_times(g, lambda: g.lmme(a, b, out=c))
+    res["lmme_32x1024^3"] = {"ms": round(sec * 1e3, 3), "tflops": round(2.0 * n ** 3 * B / sec / 1e12, 2),
+                             "pct_of_mfma_peak": round(100 * 2.0 * n ** 3 * B / sec / 1e12 / MFMA_F32_PEAK_TFLOPS, 2),
+                             "gemm_tflops": round(2.0 * n ** 3 * B / (kt["lmme_large_gemm"] * 1e-3) / 1e12, 2), "kernels_ms": kt}
+    del a, b, c
+    for T, d in ((512, 1024), (32768, 256)):
+        z = torch.empty((T, d, d), dtype=torch.complex64, device=dev)
+        for t0, x in si.device_normal_blocks(251003426 * 10 + 73, T, (d, d), dev, max(1, (1 << 26) // (d * d))):
+            g.to_goom(x, out=z[t0:t0 + x.shape[0]])
+        out = torch.empty_like(z)
+        sec = timed(torch, lambda: g.scan(z, out=out))
+        fl = 2.0 * d ** 3 * 2 * T
+        res[f"scan_T{T}_d{d}"] = {"ms": round(sec * 1e3, 3), "products_per_s": round(T / sec, 1),
+                                  "lmme_tflops_executed": round(fl / sec / 1e12, 2),
+                                  "pct_of_fp32_mfma_peak": round(100 * fl / sec / 1e12 / MFMA_F32_PEAK_TFLOPS, 2),
+                                  "kernels_ms": kernel_times(g, lambda: g.scan(z, out=out))}
+        del z, out
+        torch.cuda.empty_cache()
     return res
 
 

@@ -52,7 +52,10 @@ def test_argument_validation_without_device(lib):
     # scan
     o = ScanOpts(0, 0)
     assert lib.goom_scan(None, p, None, p, 0, 8, 8, 1, 0, C.byref(o), None, 0) == EINVAL and "positive" in err(lib)
-    assert lib.goom_scan(None, p, None, p, 4, 129, 129, 1, 0, C.byref(o), None, 0) == EUNSUP
+    assert lib.goom_scan(None, p, None, p, 4, 1025, 1025, 1, 0, C.byref(o), None, 0) == EUNSUP
+    assert lib.goom_scan(None, p, None, p, 4, 129, 129, 1, 1, C.byref(o), None, 0) == EUNSUP and "GOOM_C64" in err(lib)
+    assert lib.goom_scan(None, p, None, p, 4, 129, 129, 1, 0, C.byref(o), None, 0) == EWS  # large matrices work through a workspace
+    assert lib.goom_scan_workspace_bytes(4, 129, 129, 1, 0, C.byref(o)) > 0
     assert lib.goom_scan(None, p, None, p, 4, 8, 4, 1, 0, C.byref(o), None, 0) == EINVAL and "initial" in err(lib)
     assert lib.goom_scan(None, p, None, p, 4, 8, 8, 1, 0, C.byref(ScanOpts(0, 9)), None, 0) == EINVAL
     assert lib.goom_scan(None, p, None, p, 4, 8, 8, 1, 0, C.byref(ScanOpts(-1, 0)), None, 0) == EINVAL
@@ -65,7 +68,11 @@ def test_argument_validation_without_device(lib):
     assert lib.goom_scan(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), p, need) == EINVAL and "context" in err(lib)
     assert lib.goom_reduce(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), None, 0) == EWS
     # lmme
-    assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 0, 0, None, 0) == EUNSUP
+    assert lib.goom_lmme(None, p, p, p, 1, 2000, 8, 8, 0, 0, None, 0) == EUNSUP
+    assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 1, 0, None, 0) == EUNSUP and "GOOM_C64" in err(lib)
+    assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 0, 1, None, 0) == EUNSUP and "repair" in err(lib)
+    assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 0, 0, None, 0) == EWS
+    assert lib.goom_lmme_workspace_bytes(1, 200, 8, 8, 0, 0) > 0
     assert lib.goom_lmme(None, p, p, p, 0, 8, 8, 8, 0, 0, None, 0) == EINVAL
     assert lib.goom_lmme(None, p, p, p, 1, 8, 8, 8, 0, 2, None, 0) == EINVAL
     # affine

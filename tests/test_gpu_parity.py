@@ -641,3 +641,18 @@ def test_scan_large_matrices(G, oracle, T, d, chunk, m, batch):
         re, sg, kap = st.advance(Z[b], sample_t=sample, return_kappa=True)
         compare(out[b][sample], re, sg, kap, name=f"large scan T{T}d{d} item {b}", max_ill_fraction=0.06)
         compare(fin[b], re[-1], sg[-1], kap[-1], name=f"large reduce T{T}d{d} item {b}", max_ill_fraction=0.06)
+
+
+def test_scan_large_matrices_beyond_double_range(G, oracle):
+    # 300 factors of 256 x 256: log-magnitudes pass 830, beyond float and double range
+    T, d = 300, 256
+    Z = oracle.to_goom(si.normal_chain(si.BASE_SEED + 66, T, d))
+    out = G.scan(dev(Z))
+    sample = [0, 50, 149, 150, 151, 299]
+    re, sg, kap = oracle.ScanStream(d, scaled=True).advance(Z, sample_t=sample, return_kappa=True)
+    compare(host(out[sample]), re, sg, kap, name="large scan T300 d256", max_ill_fraction=0.06)
+    from scipy.special import digamma
+    lam = 0.5 * (math.log(2.0) + digamma(d / 2))
+    top = float(host(out[T - 1]).real.max())
+    say(f"  log-magnitude of the last prefix {top:.1f}; growth per step {top / T:.4f} (closed form {lam:.4f})")
+    assert top > 800 and abs(top / T - lam) < 0.03
