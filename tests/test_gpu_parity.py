@@ -656,3 +656,27 @@ def test_scan_large_matrices_beyond_double_range(G, oracle):
     top = float(host(out[T - 1]).real.max())
     say(f"  log-magnitude of the last prefix {top:.1f}; growth per step {top / T:.4f} (closed form {lam:.4f})")
     assert top > 800 and abs(top / T - lam) < 0.03
+
+
+def test_caller_stream_and_profile_records(G, oracle):
+    # the library enqueues on the caller's stream and never synchronises; per-kernel timings come back by label
+    import torch
+    from paper_2510_03426_amd import Goom
+    T, d = 600, 32
+    Z = dev(oracle.to_goom(si.normal_chain(si.BASE_SEED + 67, T, d)))
+    want = host(G.scan(Z, chunk_len=50))
+    side = torch.cuda.Stream()
+    g2 = Goom(0, stream=side)
+    with torch.cuda.stream(side):
+        out = g2.scan(Z, chunk_len=50)
+    side.synchronize()
+    assert np.array_equal(host(out).view(np.uint32), want.view(np.uint32))
+    g2.set_stream(torch.cuda.default_stream())
+    out2 = g2.scan(Z, chunk_len=50)
+    assert np.array_equal(host(out2).view(np.uint32), want.view(np.uint32))
+    g2.profile_enable(True)
+    g2.scan(Z, chunk_len=50)
+    recs = g2.profile_records()
+    g2.profile_enable(False)
+    labels = [l for l, _ in recs]
+    assert any("phase1" in l for l in labels) and any("phase3" in l for l in labels) and all(ms >= 0 for _, ms in recs)
