@@ -75,10 +75,9 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 // moving the state; only the chunk product T goes through LDS (it arrives row by row).
 //
 // QR by the Gram matrix: Cholesky elimination G = R^T R, one column per step, with the same
-// column operations applied to Z, which turns Z into Q = Z R^-1 in place.  Step k scales
-// column k by 1 / sqrt(pivot) and subtracts r_kj times it from every later column j; row k
-// of R and column k of Q reach the other lanes through a few words of LDS.  The pivots are
-// the squares of R's diagonal.  G is formed and eliminated in double (the double-precision
+// column operations applied to Z, which turns Z into Q = Z R^-1 in place; row k of G and
+// column k of Z reach the other lanes through a few words of LDS.  The pivots are the
+// squares of R's diagonal.  G is formed and eliminated in double (the double-precision
 // matrix instruction; its result has row 16 mt + 4 v + g in register v), so the pivots stay
 // accurate up to cond(Z)^2 of about 1e12; the columns of Z are updated in float, which
 // costs orthogonality in proportion to sqrt(largest ratio of a column's squared norm to its
@@ -92,6 +91,7 @@ template <int DP> struct Wave {
     double rperm[2][DP];  // the same with entry 16 mt + 4 v + g at position 16 mt + 4 g + v
     float qcol[2][DP];    // column k of Z at step k
     double diag[DP];      // diagonal of the Gram matrix
+    float qpanel[DP / 16][DP * 20]; // finished panels of Q, [row][column within the panel], rows padded to 20
 };
 
 // G = Z^T Z in double; G[nt][mt][v] = entry (row 16 mt + 4 v + g, column 16 nt + c)
@@ -128,77 +128,121 @@ template <int DP> __device__ void diagonal_to_lds(const d4 (&G)[DP / 16][DP / 16
     wave_sync();
 }
 
-// Elimination on (G, Z) in its square-root-free form: step k subtracts (G_kj / p_k) times
-// row / column k from every later one, p_k = G_kk being the pivot; the columns of Z are scaled
-// by 1 / sqrt(p) once at the end.  The row and the column of step k go to LDS as they are, so
-// their round trip overlaps with the reciprocal of the pivot, which is the other half of the
-// dependent chain.  piv[nt] receives the pivot of column 16 nt + c.  Returns the largest ratio
-// G_kk / p_k seen (1 for orthogonal columns).
-template <int DP> __device__ float eliminate(d4 (&G)[DP / 16][DP / 16], f4 (&Z)[DP / 16][DP / 16], double (&piv)[DP / 16],
-                                             Wave<DP> &s, int g, int c)
+// The factorisation runs panel by panel (16 columns at a time), in square-root-free form: a step
+// subtracts (G_kj / p_k) times row / column k from every later one of the panel, p_k = G_kk being the
+// pivot, and the columns are scaled by 1 / sqrt(p) at the end of the panel.  The row and the column of
+// step k go to LDS as they are, so their round trip overlaps with the reciprocal of the pivot, the
+// other half of the dependent chain.  A panel is first made orthogonal to the finished panels on the matrix unit (R_qp = Q_q^T Z_p, then
+// Z_p -= Q_q R_qp: the first product reads both operands in place, the second takes Q_q from LDS as
+// its left operand and R_qp, as the matrix instruction left it, as its right operand), then its own
+// 16 x 16 Gram matrix is eliminated as above.  A step then touches 16 columns instead of all of
+// them, and only one 16 x 16 tile of G is alive at a time.
+
+// elimination of one panel: G is its 16 x 16 Gram matrix (register v = row 4 v + g, column c),
+// Zp its columns; pivots to piv for the lanes that own the column
+template <int DP> __device__ void eliminate_panel(d4 &G, f4 (&Zp)[DP / 16], double &piv, Wave<DP> &s, int g, int c)
 {
     constexpr int KT = DP / 16;
-    double g0[KT]; // squared norms of this lane's columns before elimination
-    diagonal_to_lds<DP>(G, s, g, c);
 #pragma unroll
-    for (int nt = 0; nt < KT; ++nt) g0[nt] = s.diag[16 * nt + c];
-#pragma unroll
-    for (int k = 0; k < DP; ++k) {
-        const int kb = k / 16, ck = k % 16;
-        const int gk = ck % 4, vk = ck / 4; // row k of G: lanes with g == gk, register vk
-        const int buf = k & 1;              // two sets of LDS words, so a step need not wait for the previous one's readers
+    for (int k = 0; k < 16; ++k) {
+        const int gk = k % 4, vk = k / 4; // row k of G: lanes with g == gk, register vk
+        const int buf = k & 1;
         double *rrow = s.rrow[buf];
         double *rperm = s.rperm[buf];
         float *qcol = s.qcol[buf];
         if (g == gk) {
-#pragma unroll
-            for (int nt = kb; nt < KT; ++nt) {
-                const int j = 16 * nt + c;
-                const double r = j > k ? G[nt][kb][vk] : 0.0; // zero left of the diagonal: finished columns stay put
-                rrow[j] = r;
-                rperm[(j & ~15) | ((j & 3) << 2) | ((j >> 2) & 3)] = r;
-            }
+            const double r = c > k ? G[vk] : 0.0; // zero left of the diagonal: finished columns stay put
+            rrow[c] = r;
+            rperm[((c & 3) << 2) | (c >> 2)] = r;
         }
-        if (c == ck) {
+        if (c == k) {
 #pragma unroll
-            for (int mt = 0; mt < KT; ++mt) *reinterpret_cast<f4 *>(&qcol[16 * mt + 4 * g]) = Z[kb][mt];
+            for (int mt = 0; mt < KT; ++mt) *reinterpret_cast<f4 *>(&qcol[16 * mt + 4 * g]) = Zp[mt];
         }
-        const double pv = G[kb][kb][vk];
-        const int lo = __builtin_amdgcn_readlane((int)(__builtin_bit_cast(unsigned long long, pv) & 0xffffffffull), 16 * gk + ck);
-        const int hi = __builtin_amdgcn_readlane((int)(__builtin_bit_cast(unsigned long long, pv) >> 32), 16 * gk + ck);
+        const double pv = G[vk];
+        const int lo = __builtin_amdgcn_readlane((int)(__builtin_bit_cast(unsigned long long, pv) & 0xffffffffull), 16 * gk + k);
+        const int hi = __builtin_amdgcn_readlane((int)(__builtin_bit_cast(unsigned long long, pv) >> 32), 16 * gk + k);
         const double pivot = __builtin_bit_cast(double, ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
-        if (c == ck) piv[kb] = pivot;
-        // 1 / pivot: float reciprocal and one Newton step in double
+        if (c == k) piv = pivot;
         const bool live = pivot > 1.0e-30;
         const double r0 = (double)__builtin_amdgcn_rcpf((float)pivot);
         const double inv = live ? r0 * (2.0 - pivot * r0) : 0.0;
         wave_sync();
-        double tj[KT];
-#pragma unroll
-        for (int nt = kb; nt < KT; ++nt) tj[nt] = rrow[16 * nt + c] * inv;
-#pragma unroll
-        for (int mt = kb; mt < KT; ++mt) {
-            // this lane's rows of G are 16 mt + 4 v + g, v = 0..3: contiguous in the permuted copy
-            const d4 ri = *reinterpret_cast<const d4 *>(&rperm[16 * mt + 4 * g]);
-#pragma unroll
-            for (int nt = kb; nt < KT; ++nt) G[nt][mt] -= ri * tj[nt];
-        }
+        const double tj = rrow[c] * inv;
+        const d4 ri = *reinterpret_cast<const d4 *>(&rperm[4 * g]); // rows 4 v + g, v = 0..3
+        G -= ri * tj;
+        const float tjf = (float)tj;
 #pragma unroll
         for (int mt = 0; mt < KT; ++mt) {
             const f4 zk = *reinterpret_cast<const f4 *>(&qcol[16 * mt + 4 * g]);
-#pragma unroll
-            for (int nt = kb; nt < KT; ++nt) Z[nt][mt] -= zk * (float)tj[nt];
+            Zp[mt] -= zk * tjf;
         }
     }
     wave_sync();
+}
+
+// QR of Z in place (Z <- Q), panel by panel; piv[nt] = squared diagonal of R for column 16 nt + c.
+// Returns the largest ratio (squared column norm) / pivot, a measure of cond(Z)^2.
+template <int DP> __device__ float qr_panels(f4 (&Z)[DP / 16][DP / 16], double (&piv)[DP / 16], Wave<DP> &s, int g, int c)
+{
+    constexpr int KT = DP / 16;
+    float norm2[KT];
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) {
+        float a = 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) a = __builtin_fmaf(Z[nt][mt][v], Z[nt][mt][v], a);
+        a += __shfl_xor(a, 16, 64);
+        a += __shfl_xor(a, 32, 64);
+        norm2[nt] = a;
+    }
+#pragma unroll
+    for (int p = 0; p < KT; ++p) {
+        // orthogonal to the finished panels; twice, because one float projection leaves about
+        // 2^-24 of the panel's norm behind, which the panel's own (much smaller) remainder would magnify
+#pragma unroll
+        for (int rep = 0; rep < (p > 0 ? 2 : 0); ++rep)
+#pragma unroll
+        for (int q = 0; q < p; ++q) {
+            f4 R = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) R = mfma4(Z[q][kt][v], Z[p][kt][v], R);
+            R = -R;
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                const f4 av = *reinterpret_cast<const f4 *>(&s.qpanel[q][(16 * mt + c) * 20 + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) Z[p][mt] = mfma4(av[v], R[v], Z[p][mt]);
+            }
+        }
+        // the panel's own Gram matrix, in double
+        d4 G = {0., 0., 0., 0.};
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) G = __builtin_amdgcn_mfma_f64_16x16x4f64((double)Z[p][kt][v], (double)Z[p][kt][v], G, 0, 0, 0);
+        piv[p] = 1.0;
+        eliminate_panel<DP>(G, Z[p], piv[p], s, g, c);
+        const bool live = piv[p] > 1.0e-30;
+        const float sc = live ? __builtin_amdgcn_rsqf((float)piv[p]) : 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) Z[p][mt] *= sc;
+        if (p + 1 < KT) {
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) s.qpanel[p][(16 * mt + 4 * g + v) * 20 + c] = Z[p][mt][v];
+            wave_sync();
+        }
+    }
     float worst = 1.0f;
 #pragma unroll
     for (int nt = 0; nt < KT; ++nt) {
-        const bool live = piv[nt] > 1.0e-30;
-        const float sc = live ? __builtin_amdgcn_rsqf((float)piv[nt]) : 0.0f;
-#pragma unroll
-        for (int mt = 0; mt < KT; ++mt) Z[nt][mt] *= sc;
-        const float ratio = live ? (float)g0[nt] * __builtin_amdgcn_rcpf((float)piv[nt]) : 1.0f;
+        const float ratio = piv[nt] > 1.0e-30 ? norm2[nt] * __builtin_amdgcn_rcpf((float)piv[nt]) : 1.0f;
         worst = fmaxf(worst, ratio);
     }
 #pragma unroll
@@ -334,16 +378,11 @@ template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(Reset
     // kept as a running product of pivots (mantissa and binary exponent apart) plus a sum of
     // exponents, so that no logarithm is taken inside the chain of chunks.
     auto qr_in_place = [&](f4 (&Z)[KT][KT], const double (&colexp)[KT]) {
-        d4 G[KT][KT];
         double piv[KT], piv2[KT];
-        gram<DP>(Z, G);
-        const float amp = eliminate<DP>(G, Z, piv, s, g, c);
+        const float amp = qr_panels<DP>(Z, piv, s, g, c);
 #pragma unroll
         for (int nt = 0; nt < KT; ++nt) piv2[nt] = 1.0;
-        if (amp > 65536.0f) { // float column updates lose about sqrt(amp) 2^-24 of orthogonality: factorise Q once more
-            gram<DP>(Z, G);
-            (void)eliminate<DP>(G, Z, piv2, s, g, c);
-        }
+        if (amp > 65536.0f) (void)qr_panels<DP>(Z, piv2, s, g, c); // float column updates lose about sqrt(amp) 2^-24 of orthogonality: once more
 #pragma unroll
         for (int nt = 0; nt < KT; ++nt)
             if (piv[nt] > 1.0e-30 && piv2[nt] > 1.0e-30) {
@@ -506,14 +545,9 @@ template <int DP> __global__ __launch_bounds__(64) void lyap_step_kernel(StepArg
             }
     }
     {
-        d4 G[KT][KT];
         double piv[KT];
-        gram<DP>(Q, G);
-        const float amp = eliminate<DP>(G, Q, piv, s, g, c);
-        if (amp > 65536.0f) {
-            gram<DP>(Q, G);
-            (void)eliminate<DP>(G, Q, piv, s, g, c);
-        }
+        const float amp = qr_panels<DP>(Q, piv, s, g, c);
+        if (amp > 65536.0f) (void)qr_panels<DP>(Q, piv, s, g, c);
     }
 
     // ---- J_t as reals scaled by 2^-sh, sh from the largest entry; identity block past d
@@ -571,16 +605,11 @@ template <int DP> __global__ __launch_bounds__(64) void lyap_step_kernel(StepArg
                 for (int nt = 0; nt < KT; ++nt) Z[nt][mt] = mfma4(av[v], Q[nt][kt][v], Z[nt][mt]);
         }
     wave_sync();
-    d4 G[KT][KT];
     double piv[KT], piv2[KT];
-    gram<DP>(Z, G);
-    const float amp = eliminate<DP>(G, Z, piv, s, g, c);
+    const float amp = qr_panels<DP>(Z, piv, s, g, c);
 #pragma unroll
     for (int nt = 0; nt < KT; ++nt) piv2[nt] = 1.0;
-    if (amp > 65536.0f) {
-        gram<DP>(Z, G);
-        (void)eliminate<DP>(G, Z, piv2, s, g, c);
-    }
+    if (amp > 65536.0f) (void)qr_panels<DP>(Z, piv2, s, g, c);
     if (g == 0) {
 #pragma unroll
         for (int nt = 0; nt < KT; ++nt) {
