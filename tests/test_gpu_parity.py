@@ -680,3 +680,55 @@ def test_caller_stream_and_profile_records(G, oracle):
     g2.profile_enable(False)
     labels = [l for l, _ in recs]
     assert any("phase1" in l for l in labels) and any("phase3" in l for l in labels) and all(ms >= 0 for _, ms in recs)
+
+
+# ------------------------------------------------------------------ degenerate cases of the method
+
+@pytest.mark.parametrize("d", [1, 3, 16, 64, 200])
+def test_degenerate_chains(G, oracle, d):
+    """Zero factors, zero rows and columns, identities, permutations, scalars, single steps: results are
+    exact here (no rounding is involved, or the oracle decides), so they are compared exactly or to the
+    tolerance, and a zero must come out as (-inf, 0)."""
+    rng = np.random.default_rng(90 + d)
+    T = 12
+    x = si.normal_f32(si.BASE_SEED + 68, 14, T * d * d).reshape(T, d, d).copy()
+    # a) identities and permutations only: every prefix is a permutation matrix, exactly
+    perm = np.stack([np.eye(d, dtype=np.float32)[rng.permutation(d)] for _ in range(T)])
+    out = host(G.scan(dev(oracle.to_goom(perm)), chunk_len=5))
+    want = np.eye(d)
+    for t in range(T):
+        want = perm[t].astype(np.float64) @ want
+        assert np.array_equal(np.isneginf(out[t].real), want == 0), (d, t)
+        assert np.all(out[t].real[want != 0] == 0.0) and np.all(out[t].imag == 0.0)
+    # b) a zero factor in the middle: every later prefix is zero; before it, the oracle's values
+    xz = x.copy()
+    xz[7] = 0.0
+    Z = oracle.to_goom(xz)
+    out = host(G.scan(dev(Z), chunk_len=4))
+    assert np.all(np.isneginf(out[7:].real)) and np.all(out[7:].imag == 0)
+    re, sg, kap = oracle.scan(Z[:7], return_kappa=True)
+    compare(out[:7], re, sg, kap, name=f"before the zero factor d{d}", max_ill_fraction=0.3 if d < 4 else 0.06)
+    assert np.all(np.isneginf(host(G.reduce(dev(Z), chunk_len=4)).real))
+    # c) zero rows and zero columns inside factors (all-zero rows of a tile must not produce NaN)
+    xr = x.copy()
+    xr[2, d // 2, :] = 0.0
+    xr[5, :, 0] = 0.0
+    xr[9, d - 1, :] = 0.0
+    Z = oracle.to_goom(xr)
+    out = host(G.scan(dev(Z), chunk_len=3))
+    re, sg, kap = oracle.scan(Z, return_kappa=True)
+    assert not np.any(np.isnan(out.real))
+    assert np.array_equal(np.isneginf(out.real), np.isneginf(re))
+    compare(out, re, sg, kap, name=f"zero rows and columns d{d}", max_ill_fraction=0.3 if d < 4 else 0.08)
+    # d) a single step is the matrix itself, bit for bit where it is finite
+    Z1 = oracle.to_goom(x[:1])
+    one = host(G.scan(dev(Z1)))
+    re, sg, kap = oracle.scan(Z1, return_kappa=True)
+    compare(one, re, sg, kap, name=f"single step d{d}", max_ill_fraction=0.0)
+    # e) LMME with a zero operand, and with the identity on either side
+    A = oracle.to_goom(x[0])
+    I = oracle.to_goom(np.eye(d, dtype=np.float32))
+    Zero = oracle.to_goom(np.zeros((d, d), dtype=np.float32))
+    assert np.all(np.isneginf(host(G.lmme(dev(A), dev(Zero))).real)) and np.all(np.isneginf(host(G.lmme(dev(Zero), dev(A))).real))
+    for got in (host(G.lmme(dev(A), dev(I))), host(G.lmme(dev(I), dev(A)))):
+        assert np.array_equal(got.imag, A.imag) and np.abs(got.real - A.real).max() <= 1e-5 * max(1.0, np.abs(A.real).max())
