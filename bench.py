@@ -27,7 +27,7 @@ def main():
     ap.add_argument("--T", type=int, default=1 << 20)
     ap.add_argument("--d", type=int, default=64)
     ap.add_argument("--chunk-len", type=int, default=0)
-    ap.add_argument("--cpu-sample-steps", type=int, default=2048,
+    ap.add_argument("--cpu-sample-steps", type=int, default=16384,
                     help="leading steps of the chain the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs")

@@ -225,72 +225,69 @@ struct ChainGeom {
 };
 
 // rows of M[b][chunk * L + s], scaled; a chain whose chunk has fewer than s + 1 steps gets the identity.
-// grid (dp, chains), 256 threads.
+// One wave per row (a row is at most 1024 entries: 16 per lane), four rows per workgroup:
+// grid (dp / 4, chains), 256 threads.
 __global__ __launch_bounds__(256) void chain_convert_left_kernel(const float2 *__restrict__ M, float *__restrict__ X, double *__restrict__ shifts,
                                                                  ChainGeom q, long long s)
 {
-    __shared__ float red[4];
-    const int row = blockIdx.x, tid = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     const long long chain = blockIdx.y, item = chain / q.chunks, chunk = chain % q.chunks;
     const long long t = chunk * q.L + s;
     const bool active = s < q.L && t < q.T;
     float *xrow = X + ((size_t)chain * q.dp + row) * q.dp;
     if (!active || row >= q.d) {
-        for (int j = tid; j < q.dp; j += 256) xrow[j] = (!active && j == row && row < q.d) ? 1.0f : 0.0f;
-        if (tid == 0) shifts[(size_t)chain * q.dp + row] = 0.0;
+        for (int j = lane; j < q.dp; j += 64) xrow[j] = (!active && j == row && row < q.d) ? 1.0f : 0.0f;
+        if (lane == 0) shifts[(size_t)chain * q.dp + row] = 0.0;
         return;
     }
     const float2 *arow = M + (((size_t)item * q.T + t) * q.d + row) * q.d;
+    float2 e[16];
     float mx = -__builtin_huge_valf();
-    for (int j = tid; j < q.d; j += 256) mx = fmaxf(mx, arow[j].x);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int j = lane + 64 * r;
+        e[r] = float2{-__builtin_huge_valf(), 0.0f};
+        if (j < q.d) e[r] = arow[j];
+        mx = fmaxf(mx, e[r].x);
+    }
 #pragma unroll
     for (int sft = 32; sft >= 1; sft >>= 1) mx = fmaxf(mx, __shfl_xor(mx, sft, 64));
-    if ((tid & 63) == 0) red[tid >> 6] = mx;
-    __syncthreads();
-    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     const bool zero_row = !(mx > -__builtin_huge_valf());
     const float sh = zero_row ? 0.0f : ceilf(mx * kLog2eF);
-    for (int j = tid; j < q.dp; j += 256) {
-        float v = 0.0f;
-        if (j < q.d && !zero_row) {
-            const float2 e = arow[j];
-            v = signed_scaled(e.x, e.y, sh);
-        }
-        xrow[j] = v;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int j = lane + 64 * r;
+        if (j < q.dp) xrow[j] = (j < q.d && !zero_row) ? signed_scaled(e[r].x, e[r].y, sh) : 0.0f;
     }
-    if (tid == 0) shifts[(size_t)chain * q.dp + row] = (double)sh;
+    if (lane == 0) shifts[(size_t)chain * q.dp + row] = (double)sh;
 }
 
 // Row n of the product (state column n): out[n][i] = in[n][i] 2^(shift_i - s_n) with s_n the largest
 // exponent of in[n][i] 2^shift_i, and the column's exponent grows by s_n.  shifts: [.][len] doubles with
-// stride shift_stride per chain (0: the same vector for all), or NULL for none.
-// grid (rows, chains), 256 threads; in and out may be the same buffer.
+// stride shift_stride per chain (0: the same vector for all), or NULL for none.  One wave per row
+// (len <= 1024), four rows per workgroup: grid (rows / 4, chains), 256 threads; in and out may be the
+// same buffer.
 __global__ __launch_bounds__(256) void rescale_rows_kernel(const float *in, float *out, const double *__restrict__ shifts, long long shift_stride,
                                                            double *__restrict__ expo, int rows_padded, int len)
 {
-    __shared__ float red[4];
-    const int n = blockIdx.x, tid = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
     const long long chain = blockIdx.y;
     const float *src = in + ((size_t)chain * rows_padded + n) * len;
     float *dst = out + ((size_t)chain * rows_padded + n) * len;
     const double *sh = shifts ? shifts + (size_t)chain * shift_stride : nullptr;
     // shifts relative to their largest, so that they fit float arithmetic next to the entries' exponents
-    float v[4], rel[4];
-    double smax = -1.0e300;
+    double smax = sh ? -1.0e300 : 0.0;
     if (sh)
-        for (int i = tid; i < len; i += 256) smax = fmax(smax, sh[i]);
-    else
-        smax = 0.0;
+        for (int i = lane; i < len; i += 64) smax = fmax(smax, sh[i]);
 #pragma unroll
     for (int sft = 32; sft >= 1; sft >>= 1) smax = fmax(smax, __shfl_xor(smax, sft, 64));
-    __shared__ double dred[4];
-    if ((tid & 63) == 0) dred[tid >> 6] = smax;
-    __syncthreads();
-    smax = fmax(fmax(dred[0], dred[1]), fmax(dred[2], dred[3]));
+    float v[16], rel[16];
     float mx = -1.0e30f;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int i = tid + 256 * r;
+    for (int r = 0; r < 16; ++r) {
+        const int i = lane + 64 * r;
         v[r] = 0.0f;
         rel[r] = 0.0f;
         if (i < len) {
@@ -302,17 +299,14 @@ __global__ __launch_bounds__(256) void rescale_rows_kernel(const float *in, floa
     }
 #pragma unroll
     for (int sft = 32; sft >= 1; sft >>= 1) mx = fmaxf(mx, __shfl_xor(mx, sft, 64));
-    if ((tid & 63) == 0) red[tid >> 6] = mx;
-    __syncthreads();
-    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     const bool all_zero = !(mx > -1.0e29f);
     const float sn = all_zero ? 0.0f : mx;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int i = tid + 256 * r;
+    for (int r = 0; r < 16; ++r) {
+        const int i = lane + 64 * r;
         if (i < len) dst[i] = __builtin_ldexpf(v[r], (int)CF::clamp_shift(rel[r] - sn));
     }
-    if (tid == 0) {
+    if (lane == 0) {
         double &e = expo[(size_t)chain * rows_padded + n];
         e = all_zero ? 0.0 : e + smax + (double)sn;
     }
@@ -517,10 +511,10 @@ int run_scan_large(goom_ctx *ctx, const void *M, const void *init, void *P, long
 
     // one step of all chains of a launch: state[chain] (rows x dp) <- state A~^T, rescaled
     auto advance = [&](float *state, double *expo, int rows, const ChainGeom &q, long long chains, long long s) {
-        hipLaunchKernelGGL(chain_convert_left_kernel, dim3(dp, (unsigned)chains), dim3(256), 0, st, Mg, atil, na, q, s);
+        hipLaunchKernelGGL(chain_convert_left_kernel, dim3(dp / 4, (unsigned)chains), dim3(256), 0, st, Mg, atil, na, q, s);
         hipLaunchKernelGGL(gemm_nt_kernel, dim3(dp / BN, rows / BM, (unsigned)chains), dim3(256), 0, st, state, atil, cbuf, rows, dp, dp,
                            (long long)rows * dp, (long long)dp * dp, (long long)rows * dp);
-        hipLaunchKernelGGL(rescale_rows_kernel, dim3(rows, (unsigned)chains), dim3(256), 0, st, cbuf, state, na, (long long)dp, expo, rows, dp);
+        hipLaunchKernelGGL(rescale_rows_kernel, dim3(rows / 4, (unsigned)chains), dim3(256), 0, st, cbuf, state, na, (long long)dp, expo, rows, dp);
     };
 
     // ---- phase 1: chunk products
@@ -549,13 +543,13 @@ int run_scan_large(goom_ctx *ctx, const void *M, const void *init, void *P, long
                                s3 + (size_t)c * mp * dp, (long long)p.C * mp * dp, e3 + (size_t)c * mp, (long long)p.C * mp, mp, dp);
         if (c < p.C1) {
             // Y <- T_c Y: the exponents of T_c's columns go onto Y's rows, T_c is turned K-contiguous
-            hipLaunchKernelGGL(rescale_rows_kernel, dim3(mp, (unsigned)batch), dim3(256), 0, st, yt, yt, e1 + (size_t)c * dp, (long long)p.C1 * dp, ey,
+            hipLaunchKernelGGL(rescale_rows_kernel, dim3(mp / 4, (unsigned)batch), dim3(256), 0, st, yt, yt, e1 + (size_t)c * dp, (long long)p.C1 * dp, ey,
                                mp, dp);
             hipLaunchKernelGGL(transpose_kernel, dim3(dp / 32, dp / 32, (unsigned)batch), dim3(256), 0, st, s1 + (size_t)c * dp * dp,
                                (long long)p.C1 * dp * dp, trow, (long long)dp * dp, dp);
             hipLaunchKernelGGL(gemm_nt_kernel, dim3(dp / BN, mp / BM, (unsigned)batch), dim3(256), 0, st, yt, trow, cbuf, mp, dp, dp, (long long)mp * dp,
                                (long long)dp * dp, (long long)mp * dp);
-            hipLaunchKernelGGL(rescale_rows_kernel, dim3(mp, (unsigned)batch), dim3(256), 0, st, cbuf, yt, (const double *)nullptr, 0LL, ey, mp, dp);
+            hipLaunchKernelGGL(rescale_rows_kernel, dim3(mp / 4, (unsigned)batch), dim3(256), 0, st, cbuf, yt, (const double *)nullptr, 0LL, ey, mp, dp);
         }
     }
     if (final_only && p.C1 > 0) {
