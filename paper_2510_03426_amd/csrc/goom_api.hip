@@ -76,13 +76,17 @@ static int need_ctx(goom_ctx *ctx)
     return check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice");
 }
 
-// Chunks per batch item for the three-phase scan: enough chains to fill 256 compute
-// units, but not so many that the serial middle phase (one step per chunk) dominates:
-// the serial depth is about 2 * chunk_len + chunks, smallest near chunks = sqrt(2 T).
-static long long default_chunk_len(long long T, long long batch, long long requested)
+// Chunks per batch item for the three-phase scan: enough chains to fill the chip, but not so many
+// that the serial middle phase (one step per chunk) dominates: the serial depth is about
+// 2 * chunk_len + chunks, smallest near chunks = sqrt(2 T).  The 128-wide kernel runs one workgroup
+// per compute unit and the 64-wide one four, and their chains are long, so a partly filled last round
+// of workgroups costs a whole round: there the chain count is one full round (256 or 1024 chains).
+static long long default_chunk_len(long long T, long long batch, long long requested, int dp)
 {
     if (requested > 0) return requested < T ? requested : T;
-    long long c_occ = (8192 + batch - 1) / batch;
+    const long long slots = dp >= 128 ? 256 : dp >= 64 ? 1024 : 8192;
+    long long c_occ = slots / batch; // never more chains than one round holds
+    if (c_occ < 1) c_occ = 1;
     long long c_depth = (long long)std::ceil(std::sqrt(2.0 * (double)T));
     long long c = c_occ < c_depth ? c_occ : c_depth;
     if (c > 1024) c = 1024;
@@ -115,10 +119,10 @@ static ScanPlan plan_scan(long long T, int d, int m_tot, int m_state, long long 
                           long long requested_chunk, bool final_only)
 {
     ScanPlan p;
-    p.L = default_chunk_len(T, batch, requested_chunk);
+    p.dp = padded_dim(d);
+    p.L = default_chunk_len(T, batch, requested_chunk, p.dp);
     p.C = (T + p.L - 1) / p.L;
     p.nt = final_only ? p.C : p.C - 1;
-    p.dp = padded_dim(d);
     p.tot = fact_layout(p.dp, m_tot, dtype);
     p.car = fact_layout(p.dp, m_state, dtype);
     p.S = 0;
