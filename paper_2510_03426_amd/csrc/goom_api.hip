@@ -607,10 +607,11 @@ int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batc
     if (lmme_is_large(n, d, m)) {
         // beyond the register-resident kernels: scaled operands, a tiled GEMM and a store pass, through the workspace
         if (dtype != GOOM_C64) return fail(ctx, GOOM_EUNSUPPORTED, "shapes above %d are built for GOOM_C64 only", GOOM_MAX_DIM);
-        if (flags & GOOM_LMME_EXACT) return fail(ctx, GOOM_EUNSUPPORTED, "the repair pass is built for shapes up to %d", GOOM_MAX_DIM);
         if (int s = check_workspace(ctx, workspace, workspace_bytes, lmme_large_workspace_bytes(batch, n, d, m))) return s;
         if (int s = need_ctx(ctx)) return s;
-        return launch_lmme_large(ctx, A, B, C, batch, n, d, m, workspace);
+        if (int s = launch_lmme_large(ctx, A, B, C, batch, n, d, m, workspace)) return s;
+        if (flags & GOOM_LMME_EXACT) return launch_lmme_exact(ctx, A, B, C, batch, n, d, m, dtype);
+        return GOOM_OK;
     }
     if (int s = need_ctx(ctx)) return s;
     const size_t cb = 2 * (dtype == GOOM_C64 ? 4 : 8);

@@ -15,8 +15,8 @@
 // signed sum of exponentials), which never leaves the representable range.
 //
 // One workgroup handles a 16 x 16 block of outputs of one batch item; the rows of A and the
-// columns of B it needs are staged in LDS once.  A block whose outputs are all certified
-// returns after the test.
+// columns of B it needs are staged in LDS, up to 128 inner indices at a time.  A block whose
+// outputs are all certified returns after the first sweep.
 #include "goom_internal.h"
 
 namespace {
@@ -53,15 +53,18 @@ template <> struct Num<double> {
     __device__ static int parity(double im) { return (int)((long long)__builtin_rint(im * 0.318309886183790671538) & 1LL); }
 };
 
+constexpr int kJBlock = 128; // inner indices staged in LDS at a time
+
 template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_kernel(ExactArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int n = a.n, d = a.d, m = a.m;
-    // LDS: log-magnitudes of 16 rows of A [16][d], 16 columns of B [d][16], then their signs as bytes
+    const int jb = d < kJBlock ? d : kJBlock;
+    // LDS: log-magnitudes of 16 rows of A [16][jb], 16 columns of B [jb][16], then their signs as bytes
     R *are = reinterpret_cast<R *>(smem);
-    R *bre = are + (size_t)kTile * d;
-    unsigned char *asg = reinterpret_cast<unsigned char *>(bre + (size_t)d * kTile);
-    unsigned char *bsg = asg + (size_t)kTile * d;
+    R *bre = are + (size_t)kTile * jb;
+    unsigned char *asg = reinterpret_cast<unsigned char *>(bre + (size_t)jb * kTile);
+    unsigned char *bsg = asg + (size_t)kTile * jb;
 
     const int tid = threadIdx.x;
     const int ti = tid / kTile, tk = tid % kTile;
@@ -74,28 +77,39 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
     const R *Bb = static_cast<const R *>(a.B) + (size_t)b * d * m * 2;
     R *Cb = static_cast<R *>(a.C) + (size_t)b * n * m * 2;
 
-    for (int e = tid; e < kTile * d; e += kThreads) {
-        const int r = e / d, j = e % d;
-        const bool ok = i0 + r < n;
-        are[e] = ok ? Ab[((size_t)(i0 + r) * d + j) * 2] : Num<R>::neg_inf();
-        asg[e] = ok ? (unsigned char)Num<R>::parity(Ab[((size_t)(i0 + r) * d + j) * 2 + 1]) : 0;
-    }
-    for (int e = tid; e < d * kTile; e += kThreads) {
-        const int j = e / kTile, c = e % kTile;
-        const bool ok = k0 + c < m;
-        bre[e] = ok ? Bb[((size_t)j * m + k0 + c) * 2] : Num<R>::neg_inf();
-        bsg[e] = ok ? (unsigned char)Num<R>::parity(Bb[((size_t)j * m + k0 + c) * 2 + 1]) : 0;
-    }
-    __syncthreads();
+    // stage inner indices [j0, j0 + len) of the 16 rows of A and the 16 columns of B
+    auto stage = [&](int j0, int len) {
+        __syncthreads();
+        for (int e = tid; e < kTile * len; e += kThreads) {
+            const int r = e / len, j = e % len;
+            const bool ok = i0 + r < n;
+            are[r * jb + j] = ok ? Ab[((size_t)(i0 + r) * d + j0 + j) * 2] : Num<R>::neg_inf();
+            asg[r * jb + j] = ok ? (unsigned char)Num<R>::parity(Ab[((size_t)(i0 + r) * d + j0 + j) * 2 + 1]) : 0;
+        }
+        for (int e = tid; e < len * kTile; e += kThreads) {
+            const int j = e / kTile, c = e % kTile;
+            const bool ok = k0 + c < m;
+            bre[j * kTile + c] = ok ? Bb[((size_t)(j0 + j) * m + k0 + c) * 2] : Num<R>::neg_inf();
+            bsg[j * kTile + c] = ok ? (unsigned char)Num<R>::parity(Bb[((size_t)(j0 + j) * m + k0 + c) * 2 + 1]) : 0;
+        }
+        __syncthreads();
+    };
 
     const int i = i0 + ti, k = k0 + tk;
     const bool live = i < n && k < m;
-    // shifts of the scaled product, as the chain kernel chooses them (to within one unit)
-    R amax = Num<R>::neg_inf(), bmax = Num<R>::neg_inf();
-    for (int j = 0; j < d; ++j) {
-        const R x = are[ti * d + j], y = bre[j * kTile + tk];
-        amax = x > amax ? x : amax;
-        bmax = y > bmax ? y : bmax;
+    // first sweep over j: the shifts of the scaled product, as its kernels choose them (to within one
+    // unit), and the largest pairwise sum
+    R amax = Num<R>::neg_inf(), bmax = Num<R>::neg_inf(), mx = Num<R>::neg_inf();
+    for (int j0 = 0; j0 < d; j0 += jb) {
+        const int len = d - j0 < jb ? d - j0 : jb;
+        stage(j0, len);
+        for (int j = 0; j < len; ++j) {
+            const R x = are[ti * jb + j], y = bre[j * kTile + tk];
+            amax = x > amax ? x : amax;
+            bmax = y > bmax ? y : bmax;
+            const R z = x + y;
+            mx = z > mx ? z : mx;
+        }
     }
     bool need = false;
     if (live) {
@@ -111,26 +125,26 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
         // a zero row or column gives an exact zero either way
     }
     if (!__syncthreads_or(need ? 1 : 0)) return;
-    if (!need) return;
 
-    // definitional signed log-sum-exp, two passes
-    R mx = Num<R>::neg_inf();
-    for (int j = 0; j < d; ++j) {
-        const R z = are[ti * d + j] + bre[j * kTile + tk];
-        mx = z > mx ? z : mx;
+    // second sweep: signed sum of exponentials relative to the largest pairwise sum (every thread of the
+    // block stages; only the uncertified outputs are rewritten)
+    R sum = 0;
+    for (int j0 = 0; j0 < d; j0 += jb) {
+        const int len = d - j0 < jb ? d - j0 : jb;
+        if (d > jb) stage(j0, len); // a single block of j is still in LDS
+        if (need && mx > Num<R>::neg_inf()) {
+            for (int j = 0; j < len; ++j) {
+                const R z = are[ti * jb + j] + bre[j * kTile + tk];
+                const R t = Num<R>::exp2_((z - mx) * Num<R>::kLog2e);
+                sum += ((asg[ti * jb + j] ^ bsg[j * kTile + tk]) & 1) ? -t : t;
+            }
+        }
     }
+    if (!need) return;
     R re_out = Num<R>::neg_inf(), im_out = 0;
-    if (mx > Num<R>::neg_inf()) {
-        R sum = 0;
-        for (int j = 0; j < d; ++j) {
-            const R z = are[ti * d + j] + bre[j * kTile + tk];
-            const R t = Num<R>::exp2_((z - mx) * Num<R>::kLog2e);
-            sum += ((asg[ti * d + j] ^ bsg[j * kTile + tk]) & 1) ? -t : t;
-        }
-        if (sum != 0) {
-            re_out = mx + Num<R>::log2_(sum < 0 ? -sum : sum) * Num<R>::kLn2;
-            im_out = sum < 0 ? Num<R>::pi() : (R)0;
-        }
+    if (mx > Num<R>::neg_inf() && sum != 0) {
+        re_out = mx + Num<R>::log2_(sum < 0 ? -sum : sum) * Num<R>::kLn2;
+        im_out = sum < 0 ? Num<R>::pi() : (R)0;
     }
     Cb[((size_t)i * m + k) * 2] = re_out;
     Cb[((size_t)i * m + k) * 2 + 1] = im_out;
@@ -153,7 +167,8 @@ int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long
     const long long grid = batch * ((n + kTile - 1) / kTile) * ((m + kTile - 1) / kTile);
     if (grid > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many output blocks for one launch");
     const size_t comp = dtype == GOOM_C64 ? 4 : 8;
-    const size_t lds = 2 * (size_t)kTile * d * comp + 2 * (size_t)kTile * d;
+    const int jb = d < kJBlock ? d : kJBlock;
+    const size_t lds = 2 * (size_t)kTile * jb * comp + 2 * (size_t)kTile * jb;
     prof_begin(ctx, "lmme_exact_repair");
     if (dtype == GOOM_C64)
         hipLaunchKernelGGL(lmme_exact_kernel<float>, dim3((unsigned)grid), dim3(kThreads), lds, ctx->stream, a);

@@ -70,7 +70,6 @@ def test_argument_validation_without_device(lib):
     # lmme
     assert lib.goom_lmme(None, p, p, p, 1, 2000, 8, 8, 0, 0, None, 0) == EUNSUP
     assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 1, 0, None, 0) == EUNSUP and "GOOM_C64" in err(lib)
-    assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 0, 1, None, 0) == EUNSUP and "repair" in err(lib)
     assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 0, 0, None, 0) == EWS
     assert lib.goom_lmme_workspace_bytes(1, 200, 8, 8, 0, 0) > 0
     assert lib.goom_lmme(None, p, p, p, 0, 8, 8, 8, 0, 0, None, 0) == EINVAL

@@ -620,6 +620,14 @@ def test_lmme_large_shapes(G, oracle, shape):
         compare(np.where(certified, got, (re + 1j * np.pi * sg).astype(np.complex64)), re, sg, kap, name=f"large lmme wide {shape}",
                 max_ill_fraction=0.05)
         assert certified.mean() > 0.9
+        # with the repair pass every output is claimed, also at a spread that leaves nothing certified
+        from paper_2510_03426_amd import LMME_EXACT
+        got = host(G.lmme(dev(A2), dev(B2), flags=LMME_EXACT))
+        compare(got, re, sg, kap, name=f"large lmme wide, repaired {shape}", max_ill_fraction=0.05)
+        A3, B3 = si.wide_range_goom_pairs(si.BASE_SEED + 69, b, n, d, m, sigma=200.0, dtype=np.complex64)
+        re3, sg3, kap3 = oracle.lmme(A3, B3, return_kappa=True)
+        got3 = host(G.lmme(dev(A3), dev(B3), flags=LMME_EXACT))
+        compare(got3, re3, sg3, kap3, name=f"large lmme sigma 200, repaired {shape}", max_ill_fraction=0.05)
 
 
 @pytest.mark.parametrize("T,d,chunk,m,batch", [(24, 256, 0, None, 1), (10, 200, 3, None, 2), (9, 160, 4, 70, 1), (6, 512, 2, None, 1),
