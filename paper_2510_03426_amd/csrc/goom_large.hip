@@ -71,8 +71,21 @@ __global__ __launch_bounds__(256) void column_shift_kernel(const float2 *__restr
     const int col = blockIdx.x * 64 + cx;
     const long long b = blockIdx.y;
     float mx = -__builtin_huge_valf();
-    if (col < m)
-        for (int j = ry; j < d; j += 4) mx = fmaxf(mx, B[((size_t)b * d + j) * m + col].x);
+    if (col < m) {
+        // eight independent loads in flight per thread: the loop is bound by memory latency otherwise
+        float part[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) part[u] = -__builtin_huge_valf();
+        const float2 *base = B + (size_t)b * d * m + col;
+        int j = ry;
+        for (; j + 28 < d; j += 32) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) part[u] = fmaxf(part[u], base[(size_t)(j + 4 * u) * m].x);
+        }
+        for (; j < d; j += 4) part[0] = fmaxf(part[0], base[(size_t)j * m].x);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mx = fmaxf(mx, part[u]);
+    }
     red[ry][cx] = mx;
     __syncthreads();
     if (ry == 0 && col < cols_padded) {
@@ -123,9 +136,16 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const float *__restrict
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, c = lane & 15;
     const int wm = wave >> 1, wn = wave & 1;
-    const long long b = blockIdx.z;
-    const float *Xb = X + b * sx + (size_t)blockIdx.y * BM * K;
-    const float *Yb = Y + b * sy + (size_t)blockIdx.x * BN * K;
+    // Workgroups are handed to the eight XCDs in turn, each with its own L2: renumber them so that one
+    // XCD works on a contiguous range of tiles, whose operand panels it then shares in its L2.
+    const unsigned tiles_x = gridDim.x, tiles_y = gridDim.y;
+    const unsigned long long nwg = (unsigned long long)tiles_x * tiles_y * gridDim.z;
+    unsigned long long lin = ((unsigned long long)blockIdx.z * tiles_y + blockIdx.y) * tiles_x + blockIdx.x;
+    if (nwg % 8 == 0) lin = (lin % 8) * (nwg / 8) + lin / 8;
+    const unsigned bx = (unsigned)(lin % tiles_x), by = (unsigned)((lin / tiles_x) % tiles_y);
+    const long long b = (long long)(lin / ((unsigned long long)tiles_x * tiles_y));
+    const float *Xb = X + b * sx + (size_t)by * BM * K;
+    const float *Yb = Y + b * sy + (size_t)bx * BN * K;
     // global -> registers: the 128 x 16 tile is 512 pieces of four floats; a thread takes two
     const int r0 = tid >> 2, r1 = r0 + 64, kq = (tid & 3) * 4;
     f4 xr0, xr1, yr0, yr1;
@@ -169,7 +189,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const float *__restrict
         __syncthreads();
         buf ^= 1;
     }
-    float *Cb = Cout + b * sc + ((size_t)blockIdx.y * BM + wm * 64) * N + (size_t)blockIdx.x * BN + wn * 64;
+    float *Cb = Cout + b * sc + ((size_t)by * BM + wm * 64) * N + (size_t)bx * BN + wn * 64;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
