@@ -614,6 +614,12 @@ int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batc
         return GOOM_OK;
     }
     if (int s = need_ctx(ctx)) return s;
+    if (n == 128 && d == 128 && m == 128) {
+        // the full-size product has a kernel of its own (inner index in tiles, running rescale)
+        if (int s = launch_lmme128(ctx, A, B, C, batch, dtype)) return s;
+        if (flags & GOOM_LMME_EXACT) return launch_lmme_exact(ctx, A, B, C, batch, n, d, m, dtype);
+        return GOOM_OK;
+    }
     const size_t cb = 2 * (dtype == GOOM_C64 ? 4 : 8);
     ChainLaunch l;
     std::memset(&l, 0, sizeof l);

@@ -118,6 +118,7 @@ int launch_lmme_large(goom_ctx *ctx, const void *A, const void *B, void *C, long
 size_t scan_large_workspace_bytes(long long T, int d, int m, long long batch, long long requested_chunk, bool final_only);
 int run_scan_large(goom_ctx *ctx, const void *M, const void *init, void *P, long long T, int d, int m, long long batch,
                    long long requested_chunk, void *ws, bool final_only);
+int launch_lmme128(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int dtype);
 int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int n, int d, int m, int dtype);
 
 int launch_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, uint32_t flags);

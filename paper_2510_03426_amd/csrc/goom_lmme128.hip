@@ -1,0 +1,209 @@
+// Batched LMME of 128 x 128 x 128 operands (paper Section 3.2, eqs. 7-10), float or double components:
+// the inner index is walked in tiles of 32 with a running rescale, so that nothing has to be known
+// about a whole row or column in advance and neither operand is read twice.
+//
+// Eq. 10 lets every row of A' and every column of B' be shifted by any amount.  Here the shifts grow as
+// the tiles arrive: after tile q the accumulators hold the partial product scaled by 2^-(n_i + e_k), with
+// n_i (e_k) a whole number near the largest log2 magnitude seen so far in row i of A' (column k of B').
+// When tile q + 1 raises a maximum, the accumulators of that row (column) are scaled down by the
+// difference, an exact power of two, before its terms are added.  The state per workgroup is small
+// (a 128 x 32 tile of A~ in LDS, a 32 x 16 slice of B~ and a 128 x 16 slice of the result in the
+// registers of each wave), which leaves room for the next tile's operands to be in flight during the
+// products, and keeps the double-precision variant out of register spills.
+//
+// One workgroup (8 waves) per pair; wave w owns result columns 16 w .. 16 w + 15.
+#include "goom_chain_kernel.h"
+
+namespace {
+
+using goom_chain::Comp;
+using goom_chain::Item;
+using goom_chain::f4;
+using goom_chain::d4;
+using goom_chain::kLog2e;
+
+constexpr int kD = 128;     // all three dimensions
+constexpr int kKQ = 32;     // inner indices per tile
+constexpr int kNQ = kD / kKQ;
+constexpr int kThreads = 512;
+
+struct Lmme128Args {
+    const void *A, *B;
+    void *C;
+};
+
+template <typename R> __global__ __launch_bounds__(kThreads) void lmme_ktile_kernel(Lmme128Args a)
+{
+    typedef Comp<R> CR;
+    typedef typename CR::vec4 vec4;
+    constexpr int LDQ = kKQ + CR::kPad;
+    constexpr int LPR = kKQ / 2;             // producer lanes per row: two adjacent entries each
+    constexpr int RPP = kThreads / LPR;      // rows per pass
+    constexpr int QA = kD / RPP;             // passes = items per thread
+    constexpr size_t kTileBytes = (size_t)kD * LDQ * sizeof(R);
+    constexpr size_t kBufBytes = kTileBytes + 2 * (size_t)kD * sizeof(R);
+    extern __shared__ __align__(16) unsigned char smem[];
+    auto tile_of = [&](int b) { return reinterpret_cast<R *>(smem + (size_t)b * kBufBytes); };
+    auto nsh_of = [&](int b) { return reinterpret_cast<R *>(smem + (size_t)b * kBufBytes + kTileBytes); };          // row shifts so far
+    auto dsh_of = [&](int b) { return reinterpret_cast<R *>(smem + (size_t)b * kBufBytes + kTileBytes) + kD; };     // their change in this tile
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+    const int col = wave * 16 + c;
+    const long long pair = blockIdx.x;
+    const R *Ap = static_cast<const R *>(a.A) + (size_t)pair * kD * kD * 2;
+    const R *Bp = static_cast<const R *>(a.B) + (size_t)pair * kD * kD * 2;
+    R *Cp = static_cast<R *>(a.C) + (size_t)pair * kD * kD * 2;
+    const R kNone = (R)-1.0e30; // "no finite entry seen yet"
+
+    // producer side: this thread's rows and column pair inside a tile
+    const int prow = tid / LPR, pcj = 2 * (tid % LPR);
+    auto load_a = [&](int q, Item<R> (&it)[QA]) {
+#pragma unroll
+        for (int p = 0; p < QA; ++p) {
+            const R *gp = Ap + ((size_t)(prow + p * RPP) * kD + q * kKQ + pcj) * 2;
+            const vec4 w = *reinterpret_cast<const vec4 *>(gp);
+            it[p].re0 = w[0]; it[p].im0 = w[1]; it[p].re1 = w[2]; it[p].im1 = w[3];
+        }
+    };
+    // consumer side: rows 32 q + 16 kt + row_of(g, v) of column col
+    auto load_b = [&](int q, R (&bre)[2][4], R (&bim)[2][4]) {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const R *gp = Bp + ((size_t)(q * kKQ + 16 * kt + CR::row_of(g, v)) * kD + col) * 2;
+                bre[kt][v] = gp[0];
+                bim[kt][v] = gp[1];
+            }
+    };
+
+    R nprev[QA];
+#pragma unroll
+    for (int p = 0; p < QA; ++p) nprev[p] = kNone;
+    // tile q of A~ into buffer buf, with the running row shifts
+    auto convert_a = [&](const Item<R> (&it)[QA], int buf) {
+        R *tile = tile_of(buf);
+        R *nsh = nsh_of(buf), *dsh = dsh_of(buf);
+#pragma unroll
+        for (int p = 0; p < QA; ++p) {
+            const int row = prow + p * RPP;
+            const R mx = CR::template group_allmax<LPR>(it[p].re0, it[p].re1);
+            const R cand = mx > CR::neg_inf() ? CR::ceil_(mx * (R)kLog2e) : kNone;
+            const R nnew = cand > nprev[p] ? cand : nprev[p];
+            const R x0 = CR::apply_sign(CR::exp2_shifted(it[p].re0, nnew), it[p].im0);
+            const R x1 = CR::apply_sign(CR::exp2_shifted(it[p].re1, nnew), it[p].im1);
+            tile[row * LDQ + CR::phys(pcj)] = x0;
+            tile[row * LDQ + CR::phys(pcj + 1)] = x1;
+            nsh[CR::phys(row)] = nnew;
+            dsh[CR::phys(row)] = nprev[p] - nnew; // <= 0; hugely negative the first time a row gets entries
+            nprev[p] = nnew;
+        }
+    };
+
+    vec4 acc[kD / 16];
+#pragma unroll
+    for (int mt = 0; mt < kD / 16; ++mt) acc[mt] = vec4{0, 0, 0, 0};
+    R ecol = kNone;
+
+    Item<R> ait[QA];
+    R bre[2][4], bim[2][4];
+    load_a(0, ait);
+    load_b(0, bre, bim);
+    convert_a(ait, 0);
+    if (kNQ > 1) load_a(1, ait);
+    __syncthreads();
+
+    for (int q = 0; q < kNQ; ++q) {
+        const int buf = q & 1;
+        const R *tile = tile_of(buf);
+        const R *dsh = dsh_of(buf);
+        // ---- this tile's slice of B~ and the column's running shift
+        R cmax = CR::neg_inf();
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) cmax = CR::max_(cmax, bre[kt][v]);
+        cmax = CR::xor16_32_max(cmax);
+        const R cand = cmax > CR::neg_inf() ? CR::ceil_(cmax * (R)kLog2e) : kNone;
+        const R enew = cand > ecol ? cand : ecol;
+        const R de = ecol - enew;
+        ecol = enew;
+        R bq[2][4];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) bq[kt][v] = CR::apply_sign(CR::exp2_shifted(bre[kt][v], enew), bim[kt][v]);
+        if (q + 1 < kNQ) load_b(q + 1, bre, bim);
+        // ---- accumulators onto the new shifts (exact powers of two)
+        if (q > 0) {
+#pragma unroll
+            for (int mt = 0; mt < kD / 16; ++mt) {
+                const vec4 dn = *reinterpret_cast<const vec4 *>(&dsh[16 * mt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[mt][v] = CR::ldexp_(acc[mt][v], (int)CR::clamp_shift(dn[v] + de));
+            }
+        }
+        // ---- products
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+            vec4 av[kD / 16];
+#pragma unroll
+            for (int mt = 0; mt < kD / 16; ++mt) av[mt] = *reinterpret_cast<const vec4 *>(&tile[(16 * mt + c) * LDQ + 16 * kt + 4 * g]);
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int mt = 0; mt < kD / 16; ++mt) acc[mt] = CR::mfma(av[mt][v], bq[kt][v], acc[mt]);
+        }
+        // ---- next tile of A~ into the other buffer, the one after that on its way
+        if (q + 1 < kNQ) {
+            convert_a(ait, buf ^ 1);
+            if (q + 2 < kNQ) load_a(q + 2, ait);
+        }
+        __syncthreads();
+    }
+
+    // ---- signed logarithm, shifts re-added
+    const R *nsh = nsh_of((kNQ - 1) & 1);
+#pragma unroll
+    for (int mt = 0; mt < kD / 16; ++mt) {
+        const vec4 nv = *reinterpret_cast<const vec4 *>(&nsh[16 * mt + 4 * g]);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const R x = acc[mt][v];
+            R *op = Cp + ((size_t)(16 * mt + CR::row_of(g, v)) * kD + col) * 2;
+            const bool zero = x == (R)0;
+            op[0] = zero ? CR::neg_inf() : CR::out_re(x, nv[v], (double)ecol);
+            op[1] = x < (R)0 ? CR::pi() : (R)0;
+        }
+    }
+}
+
+template <typename R> int launch_ktile(goom_ctx *ctx, const Lmme128Args &args, long long batch)
+{
+    constexpr int LDQ = kKQ + Comp<R>::kPad;
+    const size_t lds = 2 * ((size_t)kD * LDQ * sizeof(R) + 2 * (size_t)kD * sizeof(R));
+    auto kern = lmme_ktile_kernel<R>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return goom::check_hip(ctx, e, "hipFuncSetAttribute(lmme_ktile_kernel)");
+    }
+    if (batch > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many pairs for one launch");
+    goom::prof_begin(ctx, "lmme");
+    hipLaunchKernelGGL(kern, dim3((unsigned)batch), dim3(kThreads), lds, ctx->stream, args);
+    goom::prof_end(ctx);
+    return goom::check_hip(ctx, hipGetLastError(), "launch lmme_ktile_kernel");
+}
+
+} // namespace
+
+namespace goom {
+
+int launch_lmme128(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int dtype)
+{
+    Lmme128Args args{A, B, C};
+    return dtype == GOOM_C64 ? launch_ktile<float>(ctx, args, batch) : launch_ktile<double>(ctx, args, batch);
+}
+
+} // namespace goom
