@@ -284,7 +284,8 @@ def batched_lmme(g, torch, dev, si):
                 "ms": round(sec * 1e3, 3), "pairs_per_s": round(B / sec, 1),
                 "tflops": round(2.0 * n ** 3 * B / sec / 1e12, 2),
                 "pct_of_mfma_peak": round(100 * 2.0 * n ** 3 * B / sec / 1e12 / peak, 2),
-                "hbm_gbs": round(3 * a.numel() * a.element_size() / sec / 1e9, 1)}
+                "hbm_gbs": round(3 * a.numel() * a.element_size() / sec / 1e9, 1),
+                "kernels_ms": kernel_times(g, lambda: g.lmme(a, b, flags=flags, out=c))}
         # benign range (entries N(0,1)): nothing to repair
         a = g.to_goom(torch.randn((B, n, n), device=dev, dtype=torch.float32 if name == "c64" else torch.float64))
         b = g.to_goom(torch.randn((B, n, n), device=dev, dtype=torch.float32 if name == "c64" else torch.float64))

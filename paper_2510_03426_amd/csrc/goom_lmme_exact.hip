@@ -14,10 +14,10 @@
 // others are recomputed term by term on the vector ALUs, in two passes over j (maximum, then
 // signed sum of exponentials), which never leaves the representable range.
 //
-// One workgroup handles a 16 x 16 block of outputs of one batch item; the rows of A and the
-// columns of B it needs are staged in LDS, up to 128 inner indices at a time.  A block whose
-// outputs are all certified returns after the first sweep.
-#include "goom_internal.h"
+// One workgroup handles a 64 x 64 block of outputs of one batch item, a thread 4 x 4 of them, so that
+// one pair of LDS reads serves sixteen terms; the rows of A and the columns of B are staged in LDS 32
+// inner indices at a time.  A block whose outputs are all certified returns after the first sweep.
+#include "goom_chain_kernel.h"
 
 namespace {
 
@@ -39,6 +39,7 @@ template <> struct Num<float> {
     __device__ static float neg_inf() { return -__builtin_huge_valf(); }
     __device__ static float pi() { return 3.14159274101257324219f; }
     __device__ static float exp2_(float x) { return __builtin_amdgcn_exp2f(x); }
+    __device__ static float max_(float x, float y) { return __builtin_fmaxf(x, y); }
     __device__ static float log2_(float x) { return ::log2f(x); }
     __device__ static int parity(float im) { return (int)__builtin_rintf(im * 0.318309886183790671538f) & 1; }
 };
@@ -48,106 +49,190 @@ template <> struct Num<double> {
     static constexpr double kMargin = -1022.0 + 40.0;
     __device__ static double neg_inf() { return -__builtin_huge_val(); }
     __device__ static double pi() { return 3.14159265358979311600; }
-    __device__ static double exp2_(double x) { return ::exp2(x); }
+    __device__ static double max_(double x, double y) { return __builtin_fmax(x, y); }
+    __device__ static double exp2_(double x) // x <= 0: whole part split off, short series for the rest
+    {
+        const double k = __builtin_rint(x);
+        const double y = __builtin_ldexp(goom_chain::Comp<double>::exp2_small(x - k), (int)(k > -4000.0 ? k : -4000.0));
+        return x > -1200.0 ? y : 0.0;
+    }
     __device__ static double log2_(double x) { return ::log2(x); }
     __device__ static int parity(double im) { return (int)((long long)__builtin_rint(im * 0.318309886183790671538) & 1LL); }
 };
 
-constexpr int kJBlock = 128; // inner indices staged in LDS at a time
+constexpr int kOut = 64;    // a workgroup owns a 64 x 64 block of outputs, a thread 4 x 4 of them
+constexpr int kJBlock = 32; // inner indices staged in LDS at a time
+
+template <typename R> __device__ inline R flip_sign(R x, float signword);
+template <> __device__ inline float flip_sign<float>(float x, float signword)
+{
+    return __builtin_bit_cast(float, __builtin_bit_cast(unsigned, x) ^ __builtin_bit_cast(unsigned, signword));
+}
+template <> __device__ inline double flip_sign<double>(double x, float signword)
+{
+    return __builtin_bit_cast(double, __builtin_bit_cast(unsigned long long, x) ^ ((unsigned long long)__builtin_bit_cast(unsigned, signword) << 32));
+}
 
 template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_kernel(ExactArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int n = a.n, d = a.d, m = a.m;
-    const int jb = d < kJBlock ? d : kJBlock;
-    // LDS: log-magnitudes of 16 rows of A [16][jb], 16 columns of B [jb][16], then their signs as bytes
+    constexpr int LDA = kJBlock + 1; // rows of A: [i][j], padded so that the four rows a wave reads at once differ in bank
+    // LDS: log-magnitudes of 64 rows of A [64][33] and 64 columns of B [32][64]; their signs as float +-0
     R *are = reinterpret_cast<R *>(smem);
-    R *bre = are + (size_t)kTile * jb;
-    unsigned char *asg = reinterpret_cast<unsigned char *>(bre + (size_t)jb * kTile);
-    unsigned char *bsg = asg + (size_t)kTile * jb;
+    R *bre = are + kOut * LDA;
+    float *asg = reinterpret_cast<float *>(bre + kJBlock * kOut);
+    float *bsg = asg + kOut * LDA;
 
     const int tid = threadIdx.x;
-    const int ti = tid / kTile, tk = tid % kTile;
-    const int blocks_k = (m + kTile - 1) / kTile, blocks_i = (n + kTile - 1) / kTile;
+    const int ty = tid / 16, tx = tid % 16;
+    const int blocks_k = (m + kOut - 1) / kOut, blocks_i = (n + kOut - 1) / kOut;
     const long long bid = blockIdx.x;
     const long long b = bid / ((long long)blocks_i * blocks_k);
     const int rem = (int)(bid % ((long long)blocks_i * blocks_k));
-    const int i0 = (rem / blocks_k) * kTile, k0 = (rem % blocks_k) * kTile;
+    const int i0 = (rem / blocks_k) * kOut, k0 = (rem % blocks_k) * kOut;
     const R *Ab = static_cast<const R *>(a.A) + (size_t)b * n * d * 2;
     const R *Bb = static_cast<const R *>(a.B) + (size_t)b * d * m * 2;
     R *Cb = static_cast<R *>(a.C) + (size_t)b * n * m * 2;
 
-    // stage inner indices [j0, j0 + len) of the 16 rows of A and the 16 columns of B
-    auto stage = [&](int j0, int len) {
+    // stage inner indices [j0, j0 + 32) of the 64 rows of A and the 64 columns of B (zeros past the edges)
+    auto stage = [&](int j0) {
         __syncthreads();
-        for (int e = tid; e < kTile * len; e += kThreads) {
-            const int r = e / len, j = e % len;
-            const bool ok = i0 + r < n;
-            are[r * jb + j] = ok ? Ab[((size_t)(i0 + r) * d + j0 + j) * 2] : Num<R>::neg_inf();
-            asg[r * jb + j] = ok ? (unsigned char)Num<R>::parity(Ab[((size_t)(i0 + r) * d + j0 + j) * 2 + 1]) : 0;
+        for (int e = tid; e < kOut * kJBlock; e += kThreads) {
+            const int r = e / kJBlock, j = e % kJBlock; // consecutive threads walk along a row of A
+            const bool ok = i0 + r < n && j0 + j < d;
+            R re = Num<R>::neg_inf();
+            float sg = 0.0f;
+            if (ok) {
+                const R *p = Ab + ((size_t)(i0 + r) * d + j0 + j) * 2;
+                re = p[0];
+                sg = Num<R>::parity(p[1]) ? -0.0f : 0.0f;
+            }
+            are[r * LDA + j] = re;
+            asg[r * LDA + j] = sg;
         }
-        for (int e = tid; e < len * kTile; e += kThreads) {
-            const int j = e / kTile, c = e % kTile;
-            const bool ok = k0 + c < m;
-            bre[j * kTile + c] = ok ? Bb[((size_t)(j0 + j) * m + k0 + c) * 2] : Num<R>::neg_inf();
-            bsg[j * kTile + c] = ok ? (unsigned char)Num<R>::parity(Bb[((size_t)(j0 + j) * m + k0 + c) * 2 + 1]) : 0;
+        for (int e = tid; e < kJBlock * kOut; e += kThreads) {
+            const int j = e / kOut, c = e % kOut; // consecutive threads walk along a row of B
+            const bool ok = k0 + c < m && j0 + j < d;
+            R re = Num<R>::neg_inf();
+            float sg = 0.0f;
+            if (ok) {
+                const R *p = Bb + ((size_t)(j0 + j) * m + k0 + c) * 2;
+                re = p[0];
+                sg = Num<R>::parity(p[1]) ? -0.0f : 0.0f;
+            }
+            bre[j * kOut + c] = re;
+            bsg[j * kOut + c] = sg;
         }
         __syncthreads();
     };
 
-    const int i = i0 + ti, k = k0 + tk;
-    const bool live = i < n && k < m;
-    // first sweep over j: the shifts of the scaled product, as its kernels choose them (to within one
-    // unit), and the largest pairwise sum
-    R amax = Num<R>::neg_inf(), bmax = Num<R>::neg_inf(), mx = Num<R>::neg_inf();
-    for (int j0 = 0; j0 < d; j0 += jb) {
-        const int len = d - j0 < jb ? d - j0 : jb;
-        stage(j0, len);
-        for (int j = 0; j < len; ++j) {
-            const R x = are[ti * jb + j], y = bre[j * kTile + tk];
-            amax = x > amax ? x : amax;
-            bmax = y > bmax ? y : bmax;
-            const R z = x + y;
-            mx = z > mx ? z : mx;
-        }
+    // ---- first sweep: largest pairwise sum of every output, row maxima of A and column maxima of B
+    R mx[4][4], amax[4], bmax[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        amax[r] = bmax[r] = Num<R>::neg_inf();
+#pragma unroll
+        for (int c = 0; c < 4; ++c) mx[r][c] = Num<R>::neg_inf();
     }
-    bool need = false;
-    if (live) {
-        const R cre = Cb[((size_t)i * m + k) * 2];
-        if (amax > Num<R>::neg_inf() && bmax > Num<R>::neg_inf()) {
-            const R ni = __builtin_ceil((double)amax * 1.44269504088896340736);
-            const R ek = __builtin_ceil((double)bmax * 1.44269504088896340736);
-            const R scaled = cre * Num<R>::kLog2e - ni - ek; // log2 of the scaled product's magnitude
-            R log2d = 0;
-            for (int s = 1; s < d; s <<= 1) log2d += 1;
-            need = !(scaled >= Num<R>::kMargin + log2d + 1); // also true for -inf and NaN
-        }
-        // a zero row or column gives an exact zero either way
-    }
-    if (!__syncthreads_or(need ? 1 : 0)) return;
-
-    // second sweep: signed sum of exponentials relative to the largest pairwise sum (every thread of the
-    // block stages; only the uncertified outputs are rewritten)
-    R sum = 0;
-    for (int j0 = 0; j0 < d; j0 += jb) {
-        const int len = d - j0 < jb ? d - j0 : jb;
-        if (d > jb) stage(j0, len); // a single block of j is still in LDS
-        if (need && mx > Num<R>::neg_inf()) {
-            for (int j = 0; j < len; ++j) {
-                const R z = are[ti * jb + j] + bre[j * kTile + tk];
-                const R t = Num<R>::exp2_((z - mx) * Num<R>::kLog2e);
-                sum += ((asg[ti * jb + j] ^ bsg[j * kTile + tk]) & 1) ? -t : t;
+    for (int j0 = 0; j0 < d; j0 += kJBlock) {
+        stage(j0);
+#pragma unroll 4
+        for (int j = 0; j < kJBlock; ++j) {
+            R x[4], y[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) x[r] = are[(4 * ty + r) * LDA + j];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) y[c] = bre[j * kOut + 4 * tx + c];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                amax[r] = Num<R>::max_(x[r], amax[r]);
+                bmax[r] = Num<R>::max_(y[r], bmax[r]);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) mx[r][c] = Num<R>::max_(x[r] + y[c], mx[r][c]);
             }
         }
     }
-    if (!need) return;
-    R re_out = Num<R>::neg_inf(), im_out = 0;
-    if (mx > Num<R>::neg_inf() && sum != 0) {
-        re_out = mx + Num<R>::log2_(sum < 0 ? -sum : sum) * Num<R>::kLn2;
-        im_out = sum < 0 ? Num<R>::pi() : (R)0;
+    // ---- certificate: which outputs of the scaled product may have lost terms to underflow
+    unsigned need = 0;
+    R log2d = 0;
+    for (int s = 1; s < d; s <<= 1) log2d += 1;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int i = i0 + 4 * ty + r, k = k0 + 4 * tx + c;
+            if (i < n && k < m && amax[r] > Num<R>::neg_inf() && bmax[c] > Num<R>::neg_inf()) {
+                const R cre = Cb[((size_t)i * m + k) * 2];
+                const R ni = __builtin_ceil((double)amax[r] * 1.44269504088896340736);
+                const R ek = __builtin_ceil((double)bmax[c] * 1.44269504088896340736);
+                const R scaled = cre * Num<R>::kLog2e - ni - ek; // log2 of the scaled product's magnitude
+                if (!(scaled >= Num<R>::kMargin + log2d + 1)) need |= 1u << (4 * r + c); // also for -inf and NaN
+            }
+            // a zero row or column gives an exact zero either way
+        }
+    if (!__syncthreads_or(need != 0)) return;
+
+    // ---- second sweep: signed sums of exponentials relative to the largest pairwise sum.  Every thread
+    // stages; a wave none of whose outputs needs repair skips the arithmetic.
+    const bool wave_needs = __builtin_amdgcn_ballot_w64(need != 0) != 0;
+    // which of the sixteen output positions any lane of this wave has to repair: when repairs are rare
+    // (double components), most positions are skipped by the whole wave
+    unsigned wave_mask = 0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q)
+        if (__builtin_amdgcn_ballot_w64((need >> q) & 1u) != 0) wave_mask |= 1u << q;
+    R sum[4][4], mxl[4][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            sum[r][c] = 0;
+            mxl[r][c] = mx[r][c] > Num<R>::neg_inf() ? mx[r][c] : (R)0;
+        }
+    for (int j0 = 0; j0 < d; j0 += kJBlock) {
+        if (d > kJBlock) stage(j0); // a single block of j is still in LDS
+        if (wave_needs) {
+#pragma unroll 2
+            for (int j = 0; j < kJBlock; ++j) {
+                R x[4], y[4];
+                float sx[4], sy[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    x[r] = are[(4 * ty + r) * LDA + j];
+                    sx[r] = asg[(4 * ty + r) * LDA + j];
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    y[c] = bre[j * kOut + 4 * tx + c];
+                    sy[c] = bsg[j * kOut + 4 * tx + c];
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (wave_mask & (1u << (4 * r + c))) {
+                            const R t = Num<R>::exp2_(((x[r] + y[c]) - mxl[r][c]) * Num<R>::kLog2e);
+                            sum[r][c] += flip_sign<R>(flip_sign<R>(t, sx[r]), sy[c]);
+                        }
+            }
+        }
     }
-    Cb[((size_t)i * m + k) * 2] = re_out;
-    Cb[((size_t)i * m + k) * 2 + 1] = im_out;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (need & (1u << (4 * r + c))) {
+                const int i = i0 + 4 * ty + r, k = k0 + 4 * tx + c;
+                R re_out = Num<R>::neg_inf(), im_out = 0;
+                const R sv = sum[r][c];
+                if (mx[r][c] > Num<R>::neg_inf() && sv != 0) {
+                    re_out = mx[r][c] + Num<R>::log2_(sv < 0 ? -sv : sv) * Num<R>::kLn2;
+                    im_out = sv < 0 ? Num<R>::pi() : (R)0;
+                }
+                Cb[((size_t)i * m + k) * 2] = re_out;
+                Cb[((size_t)i * m + k) * 2 + 1] = im_out;
+            }
 }
 
 } // namespace
@@ -164,11 +249,14 @@ int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long
     a.n = n;
     a.d = d;
     a.m = m;
-    const long long grid = batch * ((n + kTile - 1) / kTile) * ((m + kTile - 1) / kTile);
+    const long long grid = batch * ((n + kOut - 1) / kOut) * ((m + kOut - 1) / kOut);
     if (grid > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many output blocks for one launch");
     const size_t comp = dtype == GOOM_C64 ? 4 : 8;
-    const int jb = d < kJBlock ? d : kJBlock;
-    const size_t lds = 2 * (size_t)kTile * jb * comp + 2 * (size_t)kTile * jb;
+    const size_t lds = (size_t)kOut * (kJBlock + 1) * (comp + 4) + (size_t)kJBlock * kOut * (comp + 4) + 64;
+    if (lds > 48 * 1024) {
+        const void *kern = dtype == GOOM_C64 ? reinterpret_cast<const void *>(lmme_exact_kernel<float>) : reinterpret_cast<const void *>(lmme_exact_kernel<double>);
+        if (int st = check_hip(ctx, hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "hipFuncSetAttribute(lmme_exact_kernel)")) return st;
+    }
     prof_begin(ctx, "lmme_exact_repair");
     if (dtype == GOOM_C64)
         hipLaunchKernelGGL(lmme_exact_kernel<float>, dim3((unsigned)grid), dim3(kThreads), lds, ctx->stream, a);
