@@ -167,6 +167,11 @@ def main():
         torch.cuda.synchronize()
         cms = (time.perf_counter() - c0) / 3
         result["hbm_copy_gbs"] = round(2 * z.numel() * 8 / cms / 1e9, 1)
+        # and for reading alone (a library reduction over the first 8 GiB of the input):
+        # the ceiling for phase 1, which writes next to nothing
+        zr = torch.view_as_real(z).reshape(-1)[: 1 << 31]
+        rsec = timed(torch, lambda: zr.sum(), 5)
+        result["hbm_read_gbs"] = round(zr.numel() * 4 / rsec / 1e9, 1)
         # what the float matrix units sustain on this machine for a plain library GEMM (8192^3, float32)
         ga = torch.randn((8192, 8192), device=dev)
         gb = torch.randn((8192, 8192), device=dev)
@@ -375,6 +380,19 @@ def recurrence(g, torch, dev, si):
         "ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1),
         "hbm_gbs_algorithmic": round(byts / sec / 1e9, 1), "pct_of_hbm_peak": round(100 * byts / sec / 1e9 / HBM_PEAK_GBS, 2),
         "kernels_ms": kernel_times(g, lambda: g.affine_scan(az, bz, out=h))}
+    del h
+    # the same recurrence with its states written in scaled floating-point form by the last phase
+    sec = timed(torch, lambda: g.affine_scan_scaled(az, bz))
+    res["recurrence_scaled_states"] = {"ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1)}
+    # and with one constant matrix per sequence (no matrix traffic left)
+    a1 = az[:, 0].contiguous()
+    del az
+    torch.cuda.empty_cache()
+    h = torch.empty((nseq, T, d), dtype=torch.complex64, device=dev)
+    sec = timed(torch, lambda: g.affine_scan(a1, bz, out=h, time_invariant=True))
+    res["recurrence_time_invariant"] = {
+        "ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1),
+        "kernels_ms": kernel_times(g, lambda: g.affine_scan(a1, bz, out=h, time_invariant=True))}
     return res
 
 

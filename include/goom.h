@@ -258,6 +258,21 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
 size_t goom_affine_scan_workspace_bytes(int64_t T, int d, int64_t batch, int dtype,
                                         const goom_scan_opts *opts);
 
+/* The same recurrence with its states returned in scaled floating-point form (paper Section 4.3,
+ * eq. 21), the format the layers after the recurrence consume: scaled[b, t, i] =
+ * (+-) exp(Re h[b, t, i] - c[b, t] + 2) with c[b, t] = max_i Re h[b, t, i], all within
+ * [-e^2, e^2].  scaled: [batch, T, d] reals of the component type; logscale: NULL or [batch, T]
+ * reals receiving c (-inf for a zero state, whose scaled entries are 0).  Arguments otherwise as
+ * for goom_affine_scan.  For GOOM_C64 with d = 16 or 32 and more than one chunk the last phase
+ * writes the scaled states directly and no GOOM states touch memory; otherwise they pass through
+ * the workspace.  workspace: goom_affine_scan_scaled_workspace_bytes(...) bytes. */
+int goom_affine_scan_scaled(goom_ctx *ctx, const void *A, const void *bias, const void *h0,
+                            void *scaled, void *logscale, int64_t T, int d, int64_t batch,
+                            int dtype, const goom_scan_opts *opts, void *workspace,
+                            size_t workspace_bytes);
+size_t goom_affine_scan_scaled_workspace_bytes(int64_t T, int d, int64_t batch, int dtype,
+                                               const goom_scan_opts *opts);
+
 #pragma GCC visibility pop
 #ifdef __cplusplus
 }

@@ -27,7 +27,8 @@ EXPORTS = [
     "goom_scan_reset", "goom_scan_reset_workspace_bytes", "goom_lyapunov_spectrum",
     "goom_lyapunov_spectrum_per_step", "goom_lyapunov_spectrum_per_step_workspace_bytes",
     "goom_largest_lyapunov", "goom_largest_lyapunov_workspace_bytes",
-    "goom_affine_scan", "goom_affine_scan_workspace_bytes", "goom_scaled_exp", "goom_log_add_exp",
+    "goom_affine_scan", "goom_affine_scan_workspace_bytes", "goom_affine_scan_scaled",
+    "goom_affine_scan_scaled_workspace_bytes", "goom_scaled_exp", "goom_log_add_exp",
 ]
 
 
@@ -98,6 +99,9 @@ def load_library():
     lib.goom_affine_scan.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
     lib.goom_affine_scan_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_affine_scan_workspace_bytes.restype = sz
+    lib.goom_affine_scan_scaled.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
+    lib.goom_affine_scan_scaled_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
+    lib.goom_affine_scan_scaled_workspace_bytes.restype = sz
     _lib = lib
     return lib
 
@@ -277,6 +281,26 @@ class Goom:
         self._check(self.lib.goom_affine_scan(self._ctx, _ptr(a), _ptr(bias), _ptr(h0), _ptr(out), T, d, batch,
                                               code, C.byref(opts), _ptr(ws), wsn))
         return out
+
+    def affine_scan_scaled(self, a, bias, h0=None, chunk_len: int = 0, time_invariant: bool = False,
+                           want_logscale: bool = False):
+        """The recurrence's states as exp(h - max Re h + 2), real, and optionally the log scales."""
+        torch = self.torch
+        code = _dtype_code(a)
+        T, d = bias.shape[-2:]
+        lead = bias.shape[:-2]
+        assert a.shape == (lead + (d, d) if time_invariant else lead + (T, d, d)) and a.dtype == bias.dtype
+        batch = 1
+        for s in lead:
+            batch *= s
+        opts = ScanOpts(chunk_len, AFFINE_TIME_INVARIANT if time_invariant else 0)
+        comp = torch.float32 if a.dtype == torch.complex64 else torch.float64
+        out = torch.empty(lead + (T, d), dtype=comp, device=a.device)
+        c = torch.empty(lead + (T,), dtype=comp, device=a.device) if want_logscale else None
+        ws, wsn = self.workspace(self.lib.goom_affine_scan_scaled_workspace_bytes(T, d, batch, code, C.byref(opts)))
+        self._check(self.lib.goom_affine_scan_scaled(self._ctx, _ptr(a), _ptr(bias), _ptr(h0), _ptr(out), _ptr(c), T, d,
+                                                     batch, code, C.byref(opts), _ptr(ws), wsn))
+        return (out, c) if want_logscale else out
 
     def scan_reset(self, jac, s0=None, chunk_len: int = 0, policy: int = RESET_ALWAYS,
                    cos_threshold: float = 0.99, want_states: bool = True):

@@ -54,6 +54,8 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
     const unsigned char *left0 = a.left + item * a.left_batch_stride + t0 * a.left_step_stride;
     const float *bias0 = reinterpret_cast<const float *>(a.bias) + (size_t)(item * a.steps + t0) * DP * 2;
     float *out0 = a.out_goom ? reinterpret_cast<float *>(a.out_goom) + (size_t)(item * a.steps + t0) * DP * 2 : nullptr;
+    float *scaled0 = a.out_scaled ? a.out_scaled + (size_t)(item * a.steps + t0) * DP : nullptr;
+    float *logscale0 = a.out_logscale ? a.out_logscale + (size_t)(item * a.steps + t0) : nullptr;
 
     // starting vector: zero, or column 0 of a factored carry
     f4 hm = {0.f, 0.f, 0.f, 0.f};
@@ -194,6 +196,16 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
         hm = *reinterpret_cast<const f4 *>(&hvec[c4]);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
+        if (scaled0) {
+            // eq. 21 on the factored vector: with c = log of the largest magnitude, exp(z_i - c + 2) is the
+            // mantissa over the largest mantissa, times e^2; the vector's exponent only enters c
+            float am = C::max_(C::max_(__builtin_fabsf(hm[0]), __builtin_fabsf(hm[1])), C::max_(__builtin_fabsf(hm[2]), __builtin_fabsf(hm[3])));
+            am = C::template group_allmax<64>(am, am);
+            const float scale = am > 0.0f ? 7.38905609893065022723f / am : 0.0f;
+            if (rsub == 0) *reinterpret_cast<f4 *>(scaled0 + (size_t)t * DP + c4) = hm * scale;
+            if (logscale0 && lane == 0)
+                logscale0[t] = am > 0.0f ? (float)(((double)C::log2_abs(am) + eh) * kLn2) : -__builtin_huge_valf();
+        }
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             if (!TI) cur[q] = nxt[q];
@@ -281,8 +293,10 @@ int dispatch_affine_chunk(goom_ctx *ctx, const ChainArgs &args, int dp, long lon
 bool affine_walk_applies(const ChainArgs &args, int dp)
 {
     return (dp == 16 || dp == 32) && args.n == dp && args.d == dp && args.m == 1 && args.bias_mode == 1 &&
-           (args.init_mode == 1 || args.init_mode == 3) && (args.out_goom != nullptr || args.out_fact_final != nullptr) &&
-           !args.out_goom_last_only && args.out_fact_steps == nullptr && (args.out_goom == nullptr || args.bias_col == 0);
+           (args.init_mode == 1 || args.init_mode == 3) &&
+           (args.out_goom != nullptr || args.out_fact_final != nullptr || args.out_scaled != nullptr) &&
+           !args.out_goom_last_only && args.out_fact_steps == nullptr &&
+           ((args.out_goom == nullptr && args.out_scaled == nullptr) || args.bias_col == 0);
 }
 
 int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long nchains, const char *label)

@@ -684,20 +684,47 @@ size_t goom_affine_scan_workspace_bytes(int64_t T, int d, int64_t batch, int dty
     return p.total();
 }
 
-int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H, int64_t T, int d,
-                     int64_t batch, int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes)
+// Scaled states (eq. 21) come straight out of the matrix-vector walk where that kernel serves the
+// last phase; otherwise the states are written as GOOMs to the workspace and converted.
+static bool affine_scaled_is_fused(const ScanPlan &p, int d, int dtype) { return dtype == GOOM_C64 && (d == 16 || d == 32) && p.C > 1; }
+
+static size_t affine_states_bytes(long long T, int d, long long batch, int dtype)
+{
+    return align_up((size_t)batch * (size_t)T * (size_t)d * 2 * comp_bytes(dtype), 256);
+}
+
+size_t goom_affine_scan_scaled_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts)
+{
+    if (T <= 0 || d <= 0 || batch <= 0 || d >= GOOM_MAX_DIM) return 0;
+    if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
+    const ScanPlan p = plan_scan(T, d, d + 1, 1, batch, dtype, opts ? opts->chunk_len : 0, false);
+    return align_up(p.total(), 256) + (affine_scaled_is_fused(p, d, dtype) ? 0 : affine_states_bytes(T, d, batch, dtype));
+}
+
+static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H, void *scaled, void *logscale,
+                      int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes)
 {
     goom_scan_opts plain = opts ? *opts : goom_scan_opts{0, 0};
     const bool ti = (plain.flags & GOOM_AFFINE_TIME_INVARIANT) != 0;
     plain.flags &= ~GOOM_AFFINE_TIME_INVARIANT;
-    if (int s = check_scan_args(ctx, A, H, T, d, 1, batch, dtype, &plain)) return s;
+    const bool want_scaled = H == nullptr;
+    if (int s = check_scan_args(ctx, A, want_scaled ? scaled : H, T, d, 1, batch, dtype, &plain)) return s;
     if (!bias) return fail(ctx, GOOM_EINVAL, "null data pointer");
     if (d >= GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "the recurrence with bias needs d < %d", GOOM_MAX_DIM);
     if (!aligned(bias, 16) || (h0 && !aligned(h0, 16))) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
+    if (logscale && !aligned(logscale, comp_bytes(dtype))) return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
     const ScanPlan p = plan_scan(T, d, d + 1, 1, batch, dtype, opts ? opts->chunk_len : 0, false);
-    if (int s = check_workspace(ctx, ws, ws_bytes, p.total())) return s;
+    const bool fused = want_scaled && affine_scaled_is_fused(p, d, dtype);
+    const size_t need = want_scaled ? align_up(p.total(), 256) + (fused ? 0 : affine_states_bytes(T, d, batch, dtype)) : p.total();
+    if (int s = check_workspace(ctx, ws, ws_bytes, need)) return s;
     if (int s = need_ctx(ctx)) return s;
     const size_t cb = 2 * comp_bytes(dtype);
+    if (want_scaled && !fused) {
+        // the states as GOOMs behind the scan's own workspace, then their scaled exponentials
+        H = static_cast<unsigned char *>(ws) + align_up(p.total(), 256);
+        if (int s = run_affine(ctx, A, bias, h0, H, nullptr, nullptr, T, d, batch, dtype, opts, ws, p.total())) return s;
+        return launch_scaled_exp(ctx, H, scaled, logscale, (size_t)batch * (size_t)T, d, dtype);
+    }
 
     ChainLaunch base;
     std::memset(&base, 0, sizeof base);
@@ -796,9 +823,25 @@ int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void 
         l.fact_stride = (long long)p.car.stride;
         l.fact_cols = p.car.cols_padded;
         l.out_goom = H;
+        l.out_scaled = fused ? scaled : nullptr;
+        l.out_logscale = fused ? logscale : nullptr;
         l.label = "affine_phase3_outputs";
         return launch_chain(ctx, l);
     }
+}
+
+int goom_affine_scan(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H, int64_t T, int d,
+                     int64_t batch, int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes)
+{
+    if (!H) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    return run_affine(ctx, A, bias, h0, H, nullptr, nullptr, T, d, batch, dtype, opts, ws, ws_bytes);
+}
+
+int goom_affine_scan_scaled(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *scaled, void *logscale,
+                            int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes)
+{
+    if (!scaled) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    return run_affine(ctx, A, bias, h0, nullptr, scaled, logscale, T, d, batch, dtype, opts, ws, ws_bytes);
 }
 
 size_t goom_scan_reset_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts)

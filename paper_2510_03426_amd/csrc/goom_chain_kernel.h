@@ -53,6 +53,10 @@ struct ChainArgs {
     long long init_group;   // > 0: factored initial states come from a grouped carry array, (init_group + 1)
     long long init_ngroups; //      entries per group of init_group chunks, init_ngroups groups per batch item
     const unsigned char *bias;
+    // linear recurrence with bias, matrix-vector walk only: states in scaled floating-point form
+    // (paper eq. 21) instead of, or besides, GOOMs
+    float *out_scaled;   // NULL or [batch, steps, d]
+    float *out_logscale; // NULL or [batch, steps]
 };
 
 template <typename R> struct Comp;

@@ -83,6 +83,8 @@ struct ChainLaunch {
     int bias_mode;        // 0 none, 1 GOOM vectors [batch, steps, d], 2 column d of the factored left factor
     int bias_col;         // state column that receives the bias
     const void *bias;
+    void *out_scaled;     // NULL or float states scaled to [-e^2, e^2], [batch, steps, d] (matrix-vector walk only)
+    void *out_logscale;   // NULL or their log scales, [batch, steps]
     const char *label;    // phase name for profiling records
 };
 int launch_chain(goom_ctx *ctx, const ChainLaunch &a);

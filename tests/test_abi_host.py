@@ -77,6 +77,9 @@ def test_argument_validation_without_device(lib):
     # affine
     assert lib.goom_affine_scan(None, p, None, None, p, 4, 8, 1, 0, None, None, 0) == EINVAL
     assert lib.goom_affine_scan(None, p, p, None, p, 4, 128, 1, 0, None, None, 0) == EUNSUP
+    assert lib.goom_affine_scan(None, p, p, None, None, 4, 8, 1, 0, None, None, 0) == EINVAL
+    assert lib.goom_affine_scan_scaled(None, p, p, None, None, None, 4, 8, 1, 0, None, None, 0) == EINVAL
+    assert lib.goom_affine_scan_scaled(None, p, p, None, p, None, 4, 8, 1, 0, None, None, 0) == EWS
     # context
     assert lib.goom_create(None, 0, None) == EINVAL
     ctx = C.c_void_p()
@@ -99,7 +102,12 @@ def test_workspace_queries(lib):
     assert small == 2 * 64 * per  # 64 chunks: plain carry chain
     assert lib.goom_scan_workspace_bytes(1 << 20, 64, 64, 1, 1, C.byref(o)) > n
     assert lib.goom_scan_workspace_bytes(0, 64, 64, 1, 0, None) == 0
-    assert lib.goom_affine_scan_workspace_bytes(65536, 32, 128, 0, None) > 0
+    aff = lib.goom_affine_scan_workspace_bytes(65536, 32, 128, 0, None)
+    assert aff > 0
+    # scaled states come straight from the last phase at d = 32 (no room for GOOM states needed), at d = 8 they
+    # pass through the workspace
+    assert lib.goom_affine_scan_scaled_workspace_bytes(65536, 32, 128, 0, None) < aff + 256
+    assert lib.goom_affine_scan_scaled_workspace_bytes(65536, 8, 128, 0, None) >= 128 * 65536 * 8 * 8
     assert lib.goom_lmme_workspace_bytes(8192, 128, 128, 128, 0, 0) == 0
 
 

@@ -537,6 +537,58 @@ def test_scaled_exponentiation(G, oracle, ctype):
     assert host(H).real.max() > 700 and np.all(np.abs(got - want) <= 4 * eps * np.abs(want) + np.finfo(comp).tiny)
 
 
+@pytest.mark.parametrize("T,d,batch,chunk,ctype,ti,gain", [
+    (300, 32, 3, 32, np.complex64, False, 1.05),   # scaled states written by the walk itself
+    (1000, 16, 2, 7, np.complex64, False, 1.05),
+    (4000, 16, 2, 0, np.complex64, False, 1.3),    # magnitudes far outside float range
+    (500, 32, 2, 25, np.complex64, True, 1.0),     # constant matrix
+    (64, 8, 2, 0, np.complex64, False, 1.05),      # through GOOM states in the workspace
+    (257, 64, 1, 40, np.complex64, False, 1.05),
+    (200, 16, 2, 16, np.complex128, False, 1.05),
+    (40, 32, 2, 0, np.complex64, False, 1.05),     # a single chunk
+])
+def test_affine_scan_scaled_states(G, oracle, T, d, batch, chunk, ctype, ti, gain):
+    # eq. 21 applied to the recurrence's states inside the scan: against the oracle's states, scaled by
+    # the oracle.  An entry is compared where it and its vector's largest entry are well conditioned.
+    comp = np.float32 if ctype == np.complex64 else np.float64
+    A, b = si.recurrence_inputs(si.BASE_SEED + 57, batch, T, d, gain=gain)
+    if ti:
+        A = A[:, :1] * np.float32(0.9)
+    Az, bz = oracle.to_goom(A.astype(comp)), oracle.to_goom(b.astype(comp))
+    say(f"affine scaled T={T} d={d} batch={batch} chunk={chunk} {ctype.__name__} ti={ti}")
+    fn = lambda a_, b_: oracle.affine_scan(np.ascontiguousarray(np.broadcast_to(a_, (batch, T, d, d))), b_, h0=None, return_kappa=True)
+    re, sg, kap, well = with_sensitivity(fn, [Az, bz], comp)
+    want, cw = oracle.scaled_exp(re + 1j * np.pi * sg)
+    got, c = G.affine_scan_scaled(dev(Az[:, 0] if ti else Az), dev(bz), chunk_len=chunk, time_invariant=ti, want_logscale=True)
+    got, c = host(got).astype(np.float64), host(c).astype(np.float64)
+    assert got.shape == (batch, T, d) and c.shape == (batch, T)
+    top = np.argmax(np.where(np.isfinite(re), re, -np.inf), axis=-1)
+    top_well = np.take_along_axis(well, top[..., None], axis=-1)[..., 0]
+    ok = well & top_well[..., None]
+    assert ok.mean() > 0.8, ok.mean()
+    # the bar for log-magnitudes carried over: d(ln scaled_i) = d(re_i) - d(c), each within its tolerance
+    def bound(re_, cw_):
+        with np.errstate(invalid="ignore"):
+            return np.where(np.isfinite(re_), tolerance(re_, comp), 0.0) + tolerance(cw_, comp)[..., None]
+    ratio = (np.abs(got - want) / (bound(re, cw) * np.abs(want) + 1e-30))[ok]
+    say(f"  worst error / bound {ratio.max():.3g}")
+    assert ratio.max() <= 1
+    assert np.all(np.abs(got) <= math.e ** 2 * (1 + 1e-5))
+    assert np.all(np.abs(c - cw)[top_well] <= tolerance(cw, comp)[top_well])
+    if gain > 1.2:
+        assert cw.max() > 700
+    # without the log scales, and with an initial state
+    h0 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 58, 9, batch * d).reshape(batch, d).astype(comp))
+    fn0 = lambda a_, b_, h_: oracle.affine_scan(np.ascontiguousarray(np.broadcast_to(a_, (batch, T, d, d))), b_, h0=h_, return_kappa=True)
+    re, sg, kap, well = with_sensitivity(fn0, [Az, bz, h0], comp)
+    want, cw = oracle.scaled_exp(re + 1j * np.pi * sg)
+    got = host(G.affine_scan_scaled(dev(Az[:, 0] if ti else Az), dev(bz), dev(h0), chunk_len=chunk, time_invariant=ti)).astype(np.float64)
+    top = np.argmax(np.where(np.isfinite(re), re, -np.inf), axis=-1)
+    ok = well & np.take_along_axis(well, top[..., None], axis=-1)
+    ratio = (np.abs(got - want) / (bound(re, cw) * np.abs(want) + 1e-30))[ok]
+    assert ratio.max() <= 1
+
+
 @pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
 def test_signed_log_add(G, oracle, ctype):
     comp = np.float32 if ctype == np.complex64 else np.float64
