@@ -4,8 +4,8 @@
 //   * chunk products of the augmented matrices [A | b] (last row implicit): the hot chain
 //     kernel with one more wave for the bias column;
 //   * the walk that turns the carried vectors into all states: per chunk, h <- A_t h + b_t as a
-//     matrix-vector product.  One wave owns one chunk.  A lane loads four adjacent entries of a
-//     row of A_t (so d / 4 lanes share a row and 256 / d rows are handled per pass), scales
+//     matrix-vector product.  One wave owns one chunk.  A lane loads adjacent entries of a
+//     row of A_t (four lanes share a row, sixteen rows are handled per pass), scales
 //     them by the row's power-of-two shift, multiplies by the vector's mantissas and adds up
 //     across the row's lanes.  The vector is kept as float mantissas with one exponent for
 //     the whole vector; it goes from the lanes that own rows to the lanes that own columns
@@ -28,12 +28,20 @@ constexpr int kWalkWaves = 4; // chunks per workgroup
 
 // TI: the same matrix at every step (a time-invariant recurrence): it is loaded and scaled once,
 // and a step is a few multiply-adds per lane on registers.
+//
+// Four lanes share a row (eight adjacent entries each at d = 32, four at d = 16), so sixteen rows
+// are handled per pass and the work that is done once per row (its shift, the bias, the new
+// exponent) is repeated by few lanes.  Outputs leave through the transposed vector: after its trip
+// through LDS lane i < d holds entry i and one store instruction writes the whole state.
 template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk_kernel(ChainArgs a, long long nchains)
 {
     typedef Comp<float> C;
-    constexpr int LPR = DP / 4;   // lanes that share a row
-    constexpr int RPP = 64 / LPR; // rows per pass
-    constexpr int Q = DP / RPP;   // passes
+    constexpr int EPL = DP >= 32 ? 8 : 4; // entries of a row per lane
+    constexpr int LPR = DP / EPL;         // lanes that share a row
+    constexpr int RPP = 64 / LPR;         // rows per pass
+    constexpr int Q = DP / RPP;           // passes
+    constexpr int NV = EPL / 2;           // 16-byte pieces (two entries each) of a lane's part of a row
+    static_assert(LPR == 4 && Q >= 1 && Q * RPP == DP, "a row is shared by the four lanes of a quad");
     __shared__ __align__(16) float hvec_all[kWalkWaves][DP];
 
     const int lane = threadIdx.x & 63;
@@ -42,8 +50,9 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
     if (chain >= nchains) return; // whole wave; the kernel has no workgroup barrier
     float *hvec = hvec_all[wave];
     const int rsub = lane / LPR;
-    const int c4 = 4 * (lane % LPR);
+    const int c0 = EPL * (lane % LPR);
     const bool row_owner = (lane % LPR) == 0;
+    const bool entry_owner = lane < DP; // after the transposition lane i < d also holds entry i
 
     const long long item = chain / a.chunks_launched;
     const long long chunk = chain % a.chunks_launched;
@@ -51,14 +60,20 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
     long long len = a.steps - t0;
     if (len > a.chunk_len) len = a.chunk_len;
     if (len <= 0) return;
+    // wave-uniform bases plus 32-bit lane offsets
     const unsigned char *left0 = a.left + item * a.left_batch_stride + t0 * a.left_step_stride;
-    const float *bias0 = reinterpret_cast<const float *>(a.bias) + (size_t)(item * a.steps + t0) * DP * 2;
-    float *out0 = a.out_goom ? reinterpret_cast<float *>(a.out_goom) + (size_t)(item * a.steps + t0) * DP * 2 : nullptr;
+    const unsigned char *bias0 = a.bias + (size_t)(item * a.steps + t0) * DP * 8;
+    unsigned char *out0 = a.out_goom ? a.out_goom + (size_t)(item * a.steps + t0) * DP * 8 : nullptr;
     float *scaled0 = a.out_scaled ? a.out_scaled + (size_t)(item * a.steps + t0) * DP : nullptr;
     float *logscale0 = a.out_logscale ? a.out_logscale + (size_t)(item * a.steps + t0) : nullptr;
+    const unsigned mat_off = (unsigned)(rsub * DP + c0) * 8u; // bytes: the lane's part of row rsub
+    const unsigned bias_off = (unsigned)rsub * 8u;
+    const unsigned ent_off = (unsigned)(lane & (DP - 1));
 
     // starting vector: zero, or column 0 of a factored carry
-    f4 hm = {0.f, 0.f, 0.f, 0.f};
+    float hm[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) hm[e] = 0.0f;
     double eh = 0.0;
     if (a.init_mode == 1) {
         long long iidx = item * a.chunks_per_item + chunk;
@@ -70,54 +85,64 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
         const unsigned char *ip = a.init + iidx * a.init_stride;
         const float *mp = reinterpret_cast<const float *>(ip);
         eh = *reinterpret_cast<const double *>(ip + (size_t)DP * a.fact_cols * sizeof(float));
+        bool nz = false;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) hm[e] = mp[(size_t)(c4 + e) * a.fact_cols];
+        for (int e = 0; e < EPL; ++e) {
+            hm[e] = mp[(size_t)(c0 + e) * a.fact_cols];
+            nz = nz || hm[e] != 0.0f;
+        }
         // a zero vector carries no meaningful exponent
-        const bool nz = hm[0] != 0.0f || hm[1] != 0.0f || hm[2] != 0.0f || hm[3] != 0.0f;
         if (__builtin_amdgcn_ballot_w64(nz) == 0 || !(__builtin_fabs(eh) < 1.0e15)) eh = 0.0;
     }
 
-    Item4 cur[Q], nxt[Q];
+    f4 cur[Q][NV], nxt[Q][NV];
     float2 bcur[Q], bnxt[Q];
-    auto load_matrix = [&](long long t, Item4 (&it)[Q]) {
-        const float *src = reinterpret_cast<const float *>(left0 + t * a.left_step_stride);
+    auto load_matrix = [&](long long t, f4 (&it)[Q][NV]) {
+        const unsigned char *src = left0 + t * a.left_step_stride;
 #pragma unroll
-        for (int q = 0; q < Q; ++q) {
-            const f4 *gp = reinterpret_cast<const f4 *>(src + ((size_t)(q * RPP + rsub) * DP + c4) * 2);
-            it[q].a = gp[0];
-            it[q].b = gp[1];
-        }
+        for (int q = 0; q < Q; ++q)
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+                it[q][v] = *reinterpret_cast<const f4 *>(src + (mat_off + (unsigned)(q * RPP * DP * 8 + 16 * v)));
     };
     auto load_bias = [&](long long t, float2 (&bb)[Q]) {
-        const float *bsrc = bias0 + (size_t)t * DP * 2;
+        const unsigned char *bsrc = bias0 + (size_t)t * DP * 8;
 #pragma unroll
-        for (int q = 0; q < Q; ++q) bb[q] = *reinterpret_cast<const float2 *>(bsrc + (size_t)(q * RPP + rsub) * 2);
+        for (int q = 0; q < Q; ++q) bb[q] = *reinterpret_cast<const float2 *>(bsrc + (bias_off + (unsigned)(q * RPP * 8)));
     };
+    const float kHi = 1.44269502162933349609375f; // float nearest log2(e)
+    const float kLo = 1.925963033500011e-8f;      // log2(e) - kHi
     // the lane's entries of every row, scaled by the row's power of two and signed; the row shifts
-    float sv[Q][4], nrow[Q];
-    auto scale_rows = [&](const Item4 (&it)[Q]) {
-        const float kHi = 1.44269502162933349609375f; // float nearest log2(e)
+    float sv[Q][EPL], nrow[Q];
+    auto scale_rows = [&](const f4 (&it)[Q][NV]) {
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            const float re[4] = {it[q].a[0], it[q].a[2], it[q].b[0], it[q].b[2]};
-            const float im[4] = {it[q].a[1], it[q].a[3], it[q].b[1], it[q].b[3]};
+            float re[EPL], im[EPL];
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                re[2 * v] = it[q][v][0];
+                im[2 * v] = it[q][v][1];
+                re[2 * v + 1] = it[q][v][2];
+                im[2 * v + 1] = it[q][v][3];
+            }
             // row shift: a whole number near the row's largest log2|A_ij|
-            float u = vmax_raw(vmax_raw(re[0], re[1]), vmax_raw(re[2], re[3])) * kHi;
-            int key = C::key_of(u);
+            float u = re[0];
+#pragma unroll
+            for (int e = 1; e < EPL; ++e) u = vmax_raw(u, re[e]);
+            int key = C::key_of(u * kHi);
             key = C::imax(key, C::dpp<0xB1>(key));
             key = C::imax(key, C::dpp<0x4E>(key));
-            if (LPR >= 8) key = C::imax(key, C::dpp<0x141>(key));
-            if (LPR >= 16) key = C::imax(key, C::dpp<0x140>(key));
             const float mx = C::of_key(key);
             const bool zero_row = !(mx > -1.0e30f);
             const float n = zero_row ? 0.0f : __builtin_ceilf(mx);
             const float nsub = zero_row ? __builtin_huge_valf() : n;
             nrow[q] = n;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                // (this kernel waits on memory, so the entries get the exponential that is good to
-                // a few units in the last place at any shift rather than the cheapest one)
-                const float v = C::exp2_shifted(re[e], nsub);
+            for (int e = 0; e < EPL; ++e) {
+                // exponent argument with one rounding at its own (small) magnitude, then the low part of log2(e)
+                float t = __builtin_fmaf(re[e], kHi, -nsub);
+                t = __builtin_fmaf(re[e], kLo, t);
+                const float v = __builtin_amdgcn_exp2f(t); // 2^-inf = 0 covers zero entries and zero rows
                 const float kf = __builtin_fmaf(im[e], 0.318309886183790671538f, 12582912.0f);
                 sv[q][e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) ^ (__builtin_bit_cast(int, kf) << 31));
             }
@@ -127,56 +152,65 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
     load_bias(0, bcur);
     if (TI) scale_rows(cur);
 
-    const float kHi = 1.44269502162933349609375f; // float nearest log2(e)
-    const float kLo = 1.925963033500011e-8f;      // log2(e) - kHi
+    // A step's outputs are stored at the top of the next step, behind that step's loads: the wait for
+    // those loads then finds the stores a whole step old, not just issued (loads and stores share
+    // one counter of outstanding operations).
+    float2 pend_goom = {0.0f, 0.0f};
+    float pend_scaled = 0.0f, pend_logscale = 0.0f;
+    auto store_outputs = [&](long long t) {
+        if (out0 && entry_owner) *reinterpret_cast<float2 *>(out0 + (size_t)t * DP * 8 + ent_off * 8u) = pend_goom;
+        if (scaled0 && entry_owner) scaled0[(size_t)t * DP + ent_off] = pend_scaled;
+        if (logscale0 && lane == 0) logscale0[t] = pend_logscale;
+    };
     for (long long t = 0; t < len; ++t) {
         const long long tn = t + 1 < len ? t + 1 : len - 1;
         if (!TI) load_matrix(tn, nxt);
         load_bias(tn, bnxt);
+        if (t > 0) store_outputs(t - 1);
         if (!TI) scale_rows(cur);
         const float eh_f = (float)eh;
         float val[Q], barg[Q];
-        float bmax = -1.0e30f;
+        bool big = false;
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             float part = 0.0f;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) part = __builtin_fmaf(sv[q][e], hm[e], part);
+            for (int e = 0; e < EPL; ++e) part = __builtin_fmaf(sv[q][e], hm[e], part);
             part = add_dpp<0xB1>(part);
             part = add_dpp<0x4E>(part);
-            if (LPR >= 8) part = add_dpp<0x141>(part);
-            if (LPR >= 16) part = add_dpp<0x140>(part);
             // the row's entry of A_t h is part 2^(n + eh); the bias joins it on that scale
             float x = __builtin_fmaf(bcur[q].x, kHi, -(nrow[q] + eh_f));
             x = __builtin_fmaf(bcur[q].x, kLo, x);
             val[q] = part;
             barg[q] = x;
-            bmax = C::max_(bmax, x);
+            big = big || x > 64.0f;
         }
         // should the vector have shrunk so far below the bias that the bias would overflow on
         // its scale, the vector is scaled down first (to nothing, if need be)
-        bmax = C::template group_allmax<64>(bmax, bmax);
-        const float down = C::max_(0.0f, __builtin_ceilf(bmax) - 64.0f);
-        const int idown = -(int)C::clamp_shift(down);
-        const float ecur_f = eh_f + down;
+        float down = 0.0f;
+        if (__builtin_amdgcn_ballot_w64(big) != 0) {
+            float bmax = barg[0];
+#pragma unroll
+            for (int q = 1; q < Q; ++q) bmax = C::max_(bmax, barg[q]);
+            bmax = C::template group_allmax<64>(bmax, bmax);
+            down = C::max_(0.0f, __builtin_ceilf(bmax) - 64.0f);
+            const int idown = -(int)C::clamp_shift(down);
+#pragma unroll
+            for (int q = 0; q < Q; ++q) val[q] = __builtin_ldexpf(val[q], idown);
+        }
         float xmax = -1.0e30f;
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             const float bv = C::apply_sign(__builtin_amdgcn_exp2f(barg[q] - down), bcur[q].y);
-            val[q] = __builtin_ldexpf(val[q], idown) + bv;
-            if (out0 && row_owner) {
-                const float re = C::out_re_f(val[q], nrow[q] + ecur_f);
-                const float im = val[q] < 0.0f ? C::pi() : 0.0f;
-                *reinterpret_cast<float2 *>(out0 + ((size_t)t * DP + q * RPP + rsub) * 2) = float2{re, im};
-            }
+            val[q] += bv;
             const float ex = val[q] != 0.0f ? C::exponent_of(val[q]) + nrow[q] : -1.0e30f;
             xmax = C::max_(xmax, ex);
         }
         // new exponent of the vector: the largest entry's; mantissas at most 1 in magnitude
         {
             int key = C::key_of(xmax);
-            if (LPR < 8) key = C::imax(key, C::dpp<0x141>(key));
-            if (LPR < 16) key = C::imax(key, C::dpp<0x140>(key));
+            key = C::imax(key, C::dpp<0x141>(key));
+            key = C::imax(key, C::dpp<0x140>(key));
             key = C::xor16_imax(key);
             key = C::xor32_imax(key);
             xmax = C::of_key(key);
@@ -193,25 +227,34 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        hm = *reinterpret_cast<const f4 *>(&hvec[c4]);
+#pragma unroll
+        for (int v = 0; v < EPL / 4; ++v) {
+            const f4 h4 = *reinterpret_cast<const f4 *>(&hvec[c0 + 4 * v]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) hm[4 * v + e] = h4[e];
+        }
+        const float mine = hvec[ent_off];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
+        // the state is mantissas 2^eh
+        if (out0) pend_goom = float2{C::out_re_f(mine, (float)eh), mine < 0.0f ? C::pi() : 0.0f};
         if (scaled0) {
             // eq. 21 on the factored vector: with c = log of the largest magnitude, exp(z_i - c + 2) is the
             // mantissa over the largest mantissa, times e^2; the vector's exponent only enters c
-            float am = C::max_(C::max_(__builtin_fabsf(hm[0]), __builtin_fabsf(hm[1])), C::max_(__builtin_fabsf(hm[2]), __builtin_fabsf(hm[3])));
+            float am = __builtin_fabsf(mine);
             am = C::template group_allmax<64>(am, am);
-            const float scale = am > 0.0f ? 7.38905609893065022723f / am : 0.0f;
-            if (rsub == 0) *reinterpret_cast<f4 *>(scaled0 + (size_t)t * DP + c4) = hm * scale;
-            if (logscale0 && lane == 0)
-                logscale0[t] = am > 0.0f ? (float)(((double)C::log2_abs(am) + eh) * kLn2) : -__builtin_huge_valf();
+            pend_scaled = am > 0.0f ? mine * (7.38905609893065022723f / am) : 0.0f;
+            if (logscale0) pend_logscale = am > 0.0f ? (float)(((double)C::log2_abs(am) + eh) * kLn2) : -__builtin_huge_valf();
         }
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            if (!TI) cur[q] = nxt[q];
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+                if (!TI) cur[q][v] = nxt[q][v];
             bcur[q] = bnxt[q];
         }
     }
+    store_outputs(len - 1);
 
     if (a.out_fact_final) {
         // the chunk's vector as column bias_col of the chunk's factored total, with its own exponent
@@ -220,7 +263,7 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
         double *ep = reinterpret_cast<double *>(dst + (size_t)DP * a.fact_cols * sizeof(float));
         if (rsub == 0) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) mp[(size_t)(c4 + e) * a.fact_cols + a.bias_col] = hm[e];
+            for (int e = 0; e < EPL; ++e) mp[(size_t)(c0 + e) * a.fact_cols + a.bias_col] = hm[e];
         }
         if (lane == 0) ep[a.bias_col] = eh;
     }
