@@ -18,11 +18,6 @@ namespace goom_chain {
 namespace {
 
 
-template <int CTRL> __device__ inline float add_dpp(float x)
-{
-    const int y = __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true);
-    return x + __builtin_bit_cast(float, y);
-}
 
 constexpr int kWalkWaves = 4; // chunks per workgroup
 

@@ -3,8 +3,9 @@
 // This is the kernel the long scans spend their time in (phase 1 and phase 3 of the
 // three-phase scan; paper Section 4.1), and LMME on such shapes (Section 3.2).
 // With BIAS one more wave carries column d of the augmented state [A* | b*] of a linear
-// recurrence with bias (Section 4.3): it takes no part in converting the factor, runs the
-// same matrix instructions on its slab, and adds the step's bias vector to its column.
+// recurrence with bias (Section 4.3): it takes no part in converting the factor; its column is
+// a matrix-vector product of the same LDS tile on the vector ALU (one row per lane, or per
+// two or four lanes), to which it adds the step's bias vector.
 //
 // On this chip the float matrix instructions run at the rate of the vector ALU and do
 // not overlap with it, so a step costs (matrix cycles) + 4 x (vector instructions) and
@@ -36,8 +37,15 @@ __device__ inline float vmax_raw(float x, float y)
     return r;
 }
 
+template <int CTRL> __device__ inline float add_dpp(float x)
+{
+    const int y = __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true);
+    return x + __builtin_bit_cast(float, y);
+}
+
 template <int DP, int NW, bool BIAS>
-__global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) void chain_kernel_fast(ChainArgs a)
+// (second launch bound: waves per SIMD the register allocation has to leave room for)
+__global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 16 ? 8 : DP == 32 ? (BIAS ? 5 : 6) : DP == 64 ? (BIAS ? 3 : 4) : 2)) void chain_kernel_fast(ChainArgs a)
 {
     typedef Comp<float> C;
     constexpr int KT = DP / 16;
@@ -57,6 +65,7 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) voi
     auto tile_of = [&](int b) { return reinterpret_cast<float *>(smem + (size_t)b * kBufBytes); };
     auto nsh_of = [&](int b) { return reinterpret_cast<float *>(smem + (size_t)b * kBufBytes + kTileBytes); };
     double *wave_red = reinterpret_cast<double *>(smem + 2 * kBufBytes);
+    float *wvec = reinterpret_cast<float *>(smem + 2 * kBufBytes + 128); // the bias wave's column (BIAS only)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -67,6 +76,11 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) voi
     const int c4 = 4 * (tid % LPR); // first of this lane's four factor columns
     const bool converter = !BIAS || wave < NW;
     const bool bias_wave = BIAS && wave == NW;
+    // bias wave: lane -> row and part of the contraction index
+    constexpr int LPRB = DP >= 64 ? 1 : 64 / DP; // lanes per row
+    constexpr int CPLB = DP / LPRB;              // contraction indices per lane
+    const int brow = lane / LPRB;
+    const int bc0 = CPLB * (lane % LPRB);
 
     const long long chain = blockIdx.x;
     const long long item = chain / a.chunks_launched;
@@ -185,16 +199,13 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) voi
         convert_items(pre, 0, nullptr);
         if (len > 1) load_items(1, pre);
     }
-    // bias vector of a step, rows 16 kt + 4 g + v of this lane: (re, im) pairs, two 16-byte loads per kt
-    f4 bpre[BIAS ? KT : 1][2];
+    // bias wave: entry brow of a step's bias vector, and its column of the state (also kept in LDS,
+    // where the lanes read the entries they contract over); the column starts at zero
+    float2 bpre = {0.0f, 0.0f};
     auto load_bias = [&](long long t) {
-        const float *bp = reinterpret_cast<const float *>(a.bias) + ((size_t)(item * a.steps + t0 + t) * DP + 4 * g) * 2;
-#pragma unroll
-        for (int kt = 0; kt < KT; ++kt) {
-            bpre[kt][0] = *reinterpret_cast<const f4 *>(bp + (size_t)kt * 32);
-            bpre[kt][1] = *reinterpret_cast<const f4 *>(bp + (size_t)kt * 32 + 4);
-        }
+        bpre = *reinterpret_cast<const float2 *>(a.bias + ((size_t)(item * a.steps + t0 + t) * DP + brow) * 8);
     };
+    if (BIAS && bias_wave && lane < DP) wvec[lane] = 0.0f;
     if (BIAS && bias_wave && len > 0) load_bias(0);
     __syncthreads();
 
@@ -206,18 +217,32 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) voi
 
         // ------------------------------------------------------------ product, and next factor beside it
         f4 acc[KT];
+        float accb = 0.0f;
+        if (BIAS && bias_wave) {
+            // column d of the product: row brow of the tile times the column, on the vector ALU
 #pragma unroll
-        for (int mt = 0; mt < KT; ++mt) acc[mt] = f4{0, 0, 0, 0};
+            for (int k = 0; k < CPLB / 4; ++k) {
+                const f4 av = *reinterpret_cast<const f4 *>(&tile[brow * LDA + bc0 + 4 * k]);
+                const f4 wv = *reinterpret_cast<const f4 *>(&wvec[bc0 + 4 * k]);
 #pragma unroll
-        for (int kt = 0; kt < KT; ++kt) {
-            f4 av[KT];
+                for (int e = 0; e < 4; ++e) accb = __builtin_fmaf(av[e], wv[e], accb);
+            }
+            if (LPRB >= 2) accb = add_dpp<0xB1>(accb);
+            if (LPRB >= 4) accb = add_dpp<0x4E>(accb);
+        } else {
 #pragma unroll
-            for (int mt = 0; mt < KT; ++mt)
-                av[mt] = *reinterpret_cast<const f4 *>(&tile[(16 * mt + c) * LDA + 16 * kt + 4 * g]);
+            for (int mt = 0; mt < KT; ++mt) acc[mt] = f4{0, 0, 0, 0};
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
+            for (int kt = 0; kt < KT; ++kt) {
+                f4 av[KT];
 #pragma unroll
-                for (int mt = 0; mt < KT; ++mt) acc[mt] = C::mfma(av[mt][v], st[kt][v], acc[mt]);
+                for (int mt = 0; mt < KT; ++mt)
+                    av[mt] = *reinterpret_cast<const f4 *>(&tile[(16 * mt + c) * LDA + 16 * kt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int mt = 0; mt < KT; ++mt) acc[mt] = C::mfma(av[mt][v], st[kt][v], acc[mt]);
+            }
         }
         // (after the last product there is nothing to convert: a single product, as in a
         // batched LMME, would otherwise pay for its left factor twice)
@@ -225,46 +250,30 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) voi
             convert_items(pre, cur ^ 1, nsh);
             load_items(t + 2 < len ? t + 2 : len - 1, pre);
         }
+        float nrb = 0.0f;
         if (BIAS && bias_wave) {
-            // b_i enters entry (i, d) of the product, which is held as acc 2^(n_i + ecol): add
+            // b_i enters entry (i, d) of the product, which is held as accb 2^(n_i + ecol): add
             // (+-) 2^(log2|b_i| - n_i - ecol).  Should the column have shrunk so far below the bias
             // that this would overflow, the column is first scaled down (to nothing, if need be).
             const float kHi = 1.44269502162933349609375f;
             const float kLo = 1.925963033500011e-8f;
-            const float ecol_f = (float)ecol;
-            float arg[KT][4];
-            float amax = -1.0e30f;
-#pragma unroll
-            for (int mt = 0; mt < KT; ++mt) {
-                const f4 nv = *reinterpret_cast<const f4 *>(&nsh[16 * mt + 4 * g]);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float re = bpre[mt][v >> 1][(v & 1) * 2];
-                    float x = __builtin_fmaf(re, kHi, -(nv[v] + ecol_f));
-                    x = __builtin_fmaf(re, kLo, x);
-                    arg[mt][v] = x;
-                    amax = C::max_(amax, x);
-                }
+            nrb = nsh[brow];
+            float x = __builtin_fmaf(bpre.x, kHi, -(nrb + (float)ecol));
+            x = __builtin_fmaf(bpre.x, kLo, x);
+            float down = 0.0f;
+            if (__builtin_amdgcn_ballot_w64(x > 64.0f) != 0) {
+                const float amax = C::template group_allmax<64>(x, x);
+                down = C::max_(0.0f, __builtin_ceilf(amax) - 64.0f);
+                accb = __builtin_ldexpf(accb, -(int)C::clamp_shift(down));
+                ecol += (double)down;
             }
-            amax = C::xor16_32_max(amax);
-            const float down = C::max_(0.0f, __builtin_ceilf(amax) - 64.0f);
-            const int idown = -(int)C::clamp_shift(down);
-#pragma unroll
-            for (int mt = 0; mt < KT; ++mt)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float im = bpre[mt][v >> 1][(v & 1) * 2 + 1];
-                    const float bv = C::apply_sign(__builtin_amdgcn_exp2f(arg[mt][v] - down), im);
-                    const float sum = __builtin_ldexpf(acc[mt][v], idown) + bv;
-                    acc[mt][v] = c == 0 ? sum : acc[mt][v];
-                }
-            if (c == 0) ecol += (double)down;
+            accb += C::apply_sign(__builtin_amdgcn_exp2f(x - down), bpre.y);
             load_bias(t + 1 < len ? t + 1 : len - 1);
         }
 
         // ------------------------------------------------------------ outputs
         // entry (i = 16 mt + 4 g + v, col) of the product is acc 2^(n_i + ecol)
-        const bool want_out = a.out_goom && (!a.out_goom_last_only || last);
+        const bool want_out = a.out_goom && (!a.out_goom_last_only || last) && !bias_wave;
         if (want_out) {
             const long long o_idx = a.out_goom_last_only ? chain_global : (item * a.steps + t0 + t);
             float *outp = reinterpret_cast<float *>(a.out_goom) + ((size_t)o_idx * DP * M + (size_t)(4 * g) * M + col) * 2;
@@ -283,7 +292,24 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) voi
         }
 
         // ------------------------------------------------------------ state for the next step
-        if (!last) {
+        if (BIAS && bias_wave) {
+            // the same bookkeeping for the one column: raw between steps, renormalised now and then,
+            // row exponents folded in at the end
+            if (!last) {
+                if ((t % kRenormEvery) == kRenormEvery - 1) {
+                    float cm = C::max_(-300.0f, C::exponent_of(accb));
+                    cm = C::template group_allmax<64>(cm, cm);
+                    accb = __builtin_ldexpf(accb, -(int)cm);
+                    ecol += (double)cm;
+                }
+            } else {
+                float cm = C::exponent_of(accb) + nrb;
+                cm = C::template group_allmax<64>(cm, cm);
+                accb = __builtin_ldexpf(accb, (int)C::clamp_shift(nrb - cm));
+                ecol += (double)cm;
+            }
+            if (lane % LPRB == 0) wvec[brow] = accb;
+        } else if (!last) {
             // keep the raw product; its row exponents n_i go to the next factor's columns
 #pragma unroll
             for (int mt = 0; mt < KT; ++mt)
@@ -352,11 +378,17 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) voi
         double dsh = ecol - emax;
         dsh = dsh > -4000.0 ? dsh : -4000.0;
         const int shift = (cm > 0.0f && !bias_wave) ? (int)dsh : 0;
+        if (BIAS && bias_wave) {
+            // column d from the lanes that own its rows; the padding columns behind it are zero
+            if (lane % LPRB == 0) mp[(size_t)brow * a.fact_cols + DP] = wvec[brow];
+            for (int idx = lane; idx < DP * 15; idx += 64) mp[(size_t)(idx / 15) * a.fact_cols + DP + 1 + idx % 15] = 0.0f;
+        } else {
 #pragma unroll
-        for (int kt = 0; kt < KT; ++kt)
+            for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                mp[(size_t)(16 * kt + 4 * g + v) * a.fact_cols + col] = __builtin_ldexpf(st[kt][v], shift);
+                for (int v = 0; v < 4; ++v)
+                    mp[(size_t)(16 * kt + 4 * g + v) * a.fact_cols + col] = __builtin_ldexpf(st[kt][v], shift);
+        }
         if (g == 0) ep[col] = bias_wave ? ecol : emax;
     }
 }
@@ -364,7 +396,7 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 64 ? 2 : 1)) voi
 template <int DP, int NW, bool BIAS> int launch_fast(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
 {
     constexpr int LDA = DP + 4;
-    const size_t lds = 2 * ((size_t)DP * LDA * sizeof(float) + (size_t)DP * sizeof(float)) + 128;
+    const size_t lds = 2 * ((size_t)DP * LDA * sizeof(float) + (size_t)DP * sizeof(float)) + 128 + (BIAS ? DP * sizeof(float) : 0);
     auto kern = chain_kernel_fast<DP, NW, BIAS>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
