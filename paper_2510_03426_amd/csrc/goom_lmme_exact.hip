@@ -16,7 +16,9 @@
 //
 // One workgroup handles a 64 x 64 block of outputs of one batch item, a thread 4 x 4 of them, so that
 // one pair of LDS reads serves sixteen terms; the rows of A and the columns of B are staged in LDS 32
-// inner indices at a time.  A block whose outputs are all certified returns after the first sweep.
+// inner indices at a time.  A block whose outputs are all certified returns after the first sweep;
+// one with few outputs to repair hands them to its waves one at a time; only a block with many
+// (float components on wide-range data) runs the second sweep over all sixteen positions per thread.
 #include "goom_chain_kernel.h"
 
 namespace {
@@ -62,6 +64,7 @@ template <> struct Num<double> {
 
 constexpr int kOut = 64;    // a workgroup owns a 64 x 64 block of outputs, a thread 4 x 4 of them
 constexpr int kJBlock = 32; // inner indices staged in LDS at a time
+constexpr int kMaxList = 256; // a block with at most this many outputs to repair handles them one by one
 
 template <typename R> __device__ inline R flip_sign(R x, float signword);
 template <> __device__ inline float flip_sign<float>(float x, float signword)
@@ -171,7 +174,50 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
             }
             // a zero row or column gives an exact zero either way
         }
-    if (!__syncthreads_or(need != 0)) return;
+    // the block's outputs to repair, as a list: a short one is worked off output by output
+    __shared__ int s_count;
+    __shared__ int s_list[kMaxList];
+    if (tid == 0) s_count = 0;
+    __syncthreads();
+    for (unsigned rest = need; rest != 0; rest &= rest - 1) {
+        const int q = __builtin_ctz(rest);
+        const int slot = atomicAdd(&s_count, 1);
+        if (slot < kMaxList) s_list[slot] = (4 * ty + q / 4) * kOut + 4 * tx + q % 4;
+    }
+    __syncthreads();
+    const int count = s_count;
+    if (count == 0) return;
+    if (count <= kMaxList) {
+        // ---- few outputs (the usual case with double components): one wave per output, its lanes
+        // share the inner index; operands come straight from memory (they were read a moment ago)
+        const int lane = tid & 63, wave = tid >> 6;
+        for (int e = wave; e < count; e += kThreads / 64) {
+            const int i = i0 + s_list[e] / kOut, k = k0 + s_list[e] % kOut;
+            R zmax = Num<R>::neg_inf();
+            for (int j = lane; j < d; j += 64)
+                zmax = Num<R>::max_(zmax, Ab[((size_t)i * d + j) * 2] + Bb[((size_t)j * m + k) * 2]);
+            for (int s = 1; s < 64; s <<= 1) zmax = Num<R>::max_(zmax, __shfl_xor(zmax, s, 64));
+            R sv = 0;
+            if (zmax > Num<R>::neg_inf()) {
+                for (int j = lane; j < d; j += 64) {
+                    const R *pa = Ab + ((size_t)i * d + j) * 2, *pb = Bb + ((size_t)j * m + k) * 2;
+                    const R t = Num<R>::exp2_(((pa[0] + pb[0]) - zmax) * Num<R>::kLog2e);
+                    sv += ((Num<R>::parity(pa[1]) ^ Num<R>::parity(pb[1])) & 1) ? -t : t;
+                }
+                for (int s = 1; s < 64; s <<= 1) sv += __shfl_xor(sv, s, 64);
+            }
+            if (lane == 0) {
+                R re_out = Num<R>::neg_inf(), im_out = 0;
+                if (zmax > Num<R>::neg_inf() && sv != 0) {
+                    re_out = zmax + Num<R>::log2_(sv < 0 ? -sv : sv) * Num<R>::kLn2;
+                    im_out = sv < 0 ? Num<R>::pi() : (R)0;
+                }
+                Cb[((size_t)i * m + k) * 2] = re_out;
+                Cb[((size_t)i * m + k) * 2 + 1] = im_out;
+            }
+        }
+        return;
+    }
 
     // ---- second sweep: signed sums of exponentials relative to the largest pairwise sum.  Every thread
     // stages; a wave none of whose outputs needs repair skips the arithmetic.
