@@ -332,6 +332,76 @@ __global__ __launch_bounds__(256) void rescale_rows_kernel(const float *in, floa
     }
 }
 
+// The carry phase's pass between two products: from the raw product in[n][i] (state column n, exponent
+// ein[n]) it writes (B) the state itself, rows normalised, where the scan wants it kept, and / or (A) the
+// state with the exponents of the next left factor's columns folded onto its rows (shifts[i]), ready to be
+// multiplied.  One wave per row, four rows per workgroup: grid (rows / 4, batch), 256 threads.
+struct CarryPass {
+    const float *in; const double *ein; long long in_stride, ein_stride;
+    float *outA; double *eA; long long outA_stride, eA_stride; const double *shifts; long long shift_stride;
+    float *outB; double *eB; long long outB_stride, eB_stride;
+    int rows_padded, len;
+};
+__global__ __launch_bounds__(256) void carry_pass_kernel(CarryPass p)
+{
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long long b = blockIdx.y;
+    const float *src = p.in + b * p.in_stride + (size_t)n * p.len;
+    const double e0 = p.ein[b * p.ein_stride + n];
+    float v[16];
+    float mxB = -1.0e30f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int i = lane + 64 * r;
+        v[r] = i < p.len ? src[i] : 0.0f;
+        if (v[r] != 0.0f) mxB = fmaxf(mxB, CF::exponent_of(v[r]));
+    }
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) mxB = fmaxf(mxB, __shfl_xor(mxB, sft, 64));
+    const bool all_zero = !(mxB > -1.0e29f);
+    if (p.outB) {
+        float *dst = p.outB + b * p.outB_stride + (size_t)n * p.len;
+        const int sh = all_zero ? 0 : -(int)mxB;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = lane + 64 * r;
+            if (i < p.len) dst[i] = __builtin_ldexpf(v[r], sh);
+        }
+        if (lane == 0) p.eB[b * p.eB_stride + n] = all_zero ? 0.0 : e0 + (double)mxB;
+    }
+    if (p.outA) {
+        const double *sh = p.shifts + b * p.shift_stride;
+        double smax = -1.0e300;
+        for (int i = lane; i < p.len; i += 64) smax = fmax(smax, sh[i]);
+#pragma unroll
+        for (int sft = 32; sft >= 1; sft >>= 1) smax = fmax(smax, __shfl_xor(smax, sft, 64));
+        float rel[16];
+        float mxA = -1.0e30f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = lane + 64 * r;
+            rel[r] = 0.0f;
+            if (i < p.len) {
+                const double dr = sh[i] - smax;
+                rel[r] = dr > -4000.0 ? (float)dr : -4000.0f;
+                if (v[r] != 0.0f) mxA = fmaxf(mxA, CF::exponent_of(v[r]) + rel[r]);
+            }
+        }
+#pragma unroll
+        for (int sft = 32; sft >= 1; sft >>= 1) mxA = fmaxf(mxA, __shfl_xor(mxA, sft, 64));
+        const bool zeroA = !(mxA > -1.0e29f);
+        const float sn = zeroA ? 0.0f : mxA;
+        float *dst = p.outA + b * p.outA_stride + (size_t)n * p.len;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = lane + 64 * r;
+            if (i < p.len) dst[i] = __builtin_ldexpf(v[r], (int)CF::clamp_shift(rel[r] - sn));
+        }
+        if (lane == 0) p.eA[b * p.eA_stride + n] = zeroA ? 0.0 : e0 + smax + (double)sn;
+    }
+}
+
 // St = identity (first d rows and columns), exponents 0.  grid (rows_padded, chains), 256 threads.
 __global__ __launch_bounds__(256) void state_identity_kernel(float *St, double *expo, int rows_padded, int len, int d)
 {
@@ -445,7 +515,8 @@ namespace {
 struct LargePlan {
     long long L, C, C1; // chunk length, chunks per item, chunks whose products phase 1 forms
     int dp, mp;
-    size_t off_atil, off_na, off_s1, off_e1, off_s3, off_e3, off_cbuf, off_yt, off_ey, off_trow, total;
+    size_t off_atil, off_na, off_s1, off_e1, off_s3, off_e3, off_cbuf, off_yt, off_ey, off_trow, off_nrow, off_x2, off_ey2, total;
+    bool resident; // 128 < d <= 256 and m <= 256: the chains run with register-resident states
 };
 
 LargePlan plan_large(long long T, int d, int m, long long batch, long long requested, bool final_only)
@@ -454,7 +525,7 @@ LargePlan plan_large(long long T, int d, int m, long long batch, long long reque
     p.dp = pad_to(d, 128);
     p.mp = pad_to(m, 128);
     const long long tiles = (long long)(p.dp / 128) * (p.dp / 128);
-    const size_t per_chain = ((size_t)3 * p.dp * p.dp + (size_t)2 * p.mp * p.dp) * 4;
+    const size_t per_chain = ((size_t)4 * p.dp * p.dp + (size_t)2 * p.mp * p.dp) * 4;
     long long c;
     if (requested > 0) {
         c = (T + requested - 1) / requested;
@@ -481,21 +552,13 @@ LargePlan plan_large(long long T, int d, int m, long long batch, long long reque
     p.off_cbuf = take(chains * (size_t)(p.mp > p.dp ? p.mp : p.dp) * p.dp * 4);
     p.off_yt = take((size_t)batch * p.mp * p.dp * 4);
     p.off_ey = take((size_t)batch * p.mp * 8);
-    p.off_trow = take((size_t)batch * p.dp * p.dp * 4);
+    p.off_trow = take((size_t)batch * (p.C1 > 0 ? p.C1 : 1) * p.dp * p.dp * 4); // chunk products, transposed back
+    p.off_x2 = take((size_t)batch * p.mp * p.dp * 4); // carry phase: the operand of the next product and its exponents
+    p.off_ey2 = take((size_t)batch * p.mp * 8);
+    p.resident = p.dp == 256 && p.mp <= 256;
+    p.off_nrow = take(p.resident ? (size_t)batch * T * 256 * 4 : 0);
     p.total = off;
     return p;
-}
-
-// copies batch states (rows x len floats and rows doubles each) between strided arrays
-__global__ __launch_bounds__(256) void copy_state_kernel(const float *src, long long src_stride, const double *esrc, long long esrc_stride, float *dst,
-                                                         long long dst_stride, double *edst, long long edst_stride, int rows, int len)
-{
-    const long long b = blockIdx.y;
-    const int n = blockIdx.x;
-    const float *s = src + b * src_stride + (size_t)n * len;
-    float *t = dst + b * dst_stride + (size_t)n * len;
-    for (int i = threadIdx.x; i < len; i += 256) t[i] = s[i];
-    if (threadIdx.x == 0) edst[b * edst_stride + n] = esrc[b * esrc_stride + n];
 }
 
 } // namespace
@@ -524,6 +587,8 @@ int run_scan_large(goom_ctx *ctx, const void *M, const void *init, void *P, long
     float *yt = reinterpret_cast<float *>(w + p.off_yt);
     double *ey = reinterpret_cast<double *>(w + p.off_ey);
     float *trow = reinterpret_cast<float *>(w + p.off_trow);
+    float *cbuf2 = reinterpret_cast<float *>(w + p.off_x2);
+    double *ey2 = reinterpret_cast<double *>(w + p.off_ey2);
     const float2 *Mg = static_cast<const float2 *>(M);
     const int dp = p.dp, mp = p.mp;
     hipStream_t st = ctx->stream;
@@ -537,13 +602,25 @@ int run_scan_large(goom_ctx *ctx, const void *M, const void *init, void *P, long
         hipLaunchKernelGGL(rescale_rows_kernel, dim3(rows / 4, (unsigned)chains), dim3(256), 0, st, cbuf, state, na, (long long)dp, expo, rows, dp);
     };
 
+    float *nrow = reinterpret_cast<float *>(w + p.off_nrow);
+    if (p.resident) {
+        prof_begin(ctx, "scan_large_row_shifts");
+        const int e = launch_row_shifts256(ctx, M, nrow, d, batch * T);
+        prof_end(ctx);
+        if (e) return e;
+    }
+
     // ---- phase 1: chunk products
     if (p.C1 > 0) {
         ChainGeom q{T, p.L, p.C1, d, dp};
         const long long chains = batch * p.C1;
         prof_begin(ctx, "scan_large_phase1_chunk_products");
-        hipLaunchKernelGGL(state_identity_kernel, dim3(dp, (unsigned)chains), dim3(256), 0, st, s1, e1, dp, dp, d);
-        for (long long s = 0; s < p.L; ++s) advance(s1, e1, dp, q, chains, s);
+        if (p.resident) {
+            if (int e = launch_chain256(ctx, M, nrow, T, p.L, p.C1, batch, d, d, nullptr, nullptr, s1, e1, nullptr)) return e;
+        } else {
+            hipLaunchKernelGGL(state_identity_kernel, dim3(dp, (unsigned)chains), dim3(256), 0, st, s1, e1, dp, dp, d);
+            for (long long s = 0; s < p.L; ++s) advance(s1, e1, dp, q, chains, s);
+        }
         prof_end(ctx);
         if (int e = ok("scan_large phase 1")) return e;
     }
@@ -557,20 +634,31 @@ int run_scan_large(goom_ctx *ctx, const void *M, const void *init, void *P, long
     } else {
         hipLaunchKernelGGL(state_identity_kernel, dim3(mp, (unsigned)batch), dim3(256), 0, st, yt, ey, mp, dp, d);
     }
-    for (long long c = 0; c < p.C; ++c) {
-        if (!final_only)
-            hipLaunchKernelGGL(copy_state_kernel, dim3(mp, (unsigned)batch), dim3(256), 0, st, yt, (long long)mp * dp, ey, (long long)mp,
-                               s3 + (size_t)c * mp * dp, (long long)p.C * mp * dp, e3 + (size_t)c * mp, (long long)p.C * mp, mp, dp);
-        if (c < p.C1) {
-            // Y <- T_c Y: the exponents of T_c's columns go onto Y's rows, T_c is turned K-contiguous
-            hipLaunchKernelGGL(rescale_rows_kernel, dim3(mp / 4, (unsigned)batch), dim3(256), 0, st, yt, yt, e1 + (size_t)c * dp, (long long)p.C1 * dp, ey,
-                               mp, dp);
-            hipLaunchKernelGGL(transpose_kernel, dim3(dp / 32, dp / 32, (unsigned)batch), dim3(256), 0, st, s1 + (size_t)c * dp * dp,
-                               (long long)p.C1 * dp * dp, trow, (long long)dp * dp, dp);
-            hipLaunchKernelGGL(gemm_nt_kernel, dim3(dp / BN, mp / BM, (unsigned)batch), dim3(256), 0, st, yt, trow, cbuf, mp, dp, dp, (long long)mp * dp,
-                               (long long)dp * dp, (long long)mp * dp);
-            hipLaunchKernelGGL(rescale_rows_kernel, dim3(mp / 4, (unsigned)batch), dim3(256), 0, st, cbuf, yt, (const double *)nullptr, 0LL, ey, mp, dp);
-        }
+    // Y <- T_c Y for c = 0, 1, ...: the exponents of T_c's columns go onto Y's rows, T_c (held transposed, as a
+    // state) is turned K-contiguous again; two launches per chunk.  The scan keeps every Y (the carry into chunk c).
+    if (p.C1 > 0)
+        hipLaunchKernelGGL(transpose_kernel, dim3(dp / 32, dp / 32, (unsigned)(batch * p.C1)), dim3(256), 0, st, s1, (long long)dp * dp, trow,
+                           (long long)dp * dp, dp);
+    auto pass = [&](const float *in, const double *ein, long long c_next) {
+        // from `in`: the carry into chunk c_next (kept, for a scan) and the operand of the product with T_c_next
+        CarryPass cp;
+        cp.in = in; cp.ein = ein; cp.in_stride = (long long)mp * dp; cp.ein_stride = (long long)mp;
+        const bool more = c_next < p.C1;
+        cp.outA = more ? cbuf2 : nullptr; cp.eA = ey2; cp.outA_stride = (long long)mp * dp; cp.eA_stride = (long long)mp;
+        cp.shifts = more ? e1 + (size_t)c_next * dp : nullptr; cp.shift_stride = (long long)p.C1 * dp;
+        const bool keep = !final_only;
+        cp.outB = keep ? s3 + (size_t)c_next * mp * dp : (more ? nullptr : yt);
+        cp.eB = keep ? e3 + (size_t)c_next * mp : ey;
+        cp.outB_stride = keep ? (long long)p.C * mp * dp : (long long)mp * dp;
+        cp.eB_stride = keep ? (long long)p.C * mp : (long long)mp;
+        cp.rows_padded = mp; cp.len = dp;
+        if (cp.outA || cp.outB) hipLaunchKernelGGL(carry_pass_kernel, dim3(mp / 4, (unsigned)batch), dim3(256), 0, st, cp);
+    };
+    pass(yt, ey, 0);
+    for (long long c = 0; c < p.C1; ++c) {
+        hipLaunchKernelGGL(gemm_nt_kernel, dim3(dp / BN, mp / BM, (unsigned)batch), dim3(256), 0, st, cbuf2, trow + (size_t)c * dp * dp, cbuf, mp, dp, dp,
+                           (long long)mp * dp, (long long)p.C1 * dp * dp, (long long)mp * dp);
+        pass(cbuf, ey2, c + 1);
     }
     if (final_only && p.C1 > 0) {
         ChainGeom q{T, p.L, 1, d, dp};
@@ -587,7 +675,13 @@ int run_scan_large(goom_ctx *ctx, const void *M, const void *init, void *P, long
         float *state = final_only ? yt : s3; // a reduction of a single chunk walks it here
         double *expo = final_only ? ey : e3;
         prof_begin(ctx, final_only ? "scan_large_single_chunk" : "scan_large_phase3_outputs");
-        for (long long s = 0; s < p.L; ++s) {
+        if (p.resident) {
+            // (a reduction of a single chunk leaves its product in the state, stored below)
+            const int e = final_only ? launch_chain256(ctx, M, nrow, T, p.L, p.C, batch, d, m, state, expo, state, expo, nullptr)
+                                     : launch_chain256(ctx, M, nrow, T, p.L, p.C, batch, d, m, state, expo, nullptr, nullptr, P);
+            if (e) return e;
+        }
+        for (long long s = 0; s < (p.resident ? 0 : p.L); ++s) {
             advance(state, expo, mp, q, chains_all, s);
             if (!final_only)
                 hipLaunchKernelGGL(chain_store_kernel, dim3((d + 31) / 32, (m + 31) / 32, (unsigned)chains_all), dim3(256), 0, st, state, expo,

@@ -683,7 +683,7 @@ def test_lmme_large_shapes(G, oracle, shape):
 
 
 @pytest.mark.parametrize("T,d,chunk,m,batch", [(24, 256, 0, None, 1), (10, 200, 3, None, 2), (9, 160, 4, 70, 1), (6, 512, 2, None, 1),
-                                               (5, 300, 5, 300, 1), (3, 1024, 0, None, 1)])
+                                               (5, 300, 5, 300, 1), (3, 1024, 0, None, 1), (7, 131, 3, 5, 1), (5, 255, 2, 129, 1)])
 def test_scan_large_matrices(G, oracle, T, d, chunk, m, batch):
     say(f"large scan T={T} d={d} chunk={chunk} m={m} batch={batch}")
     for b in range(batch):
