@@ -167,11 +167,11 @@ def main():
         torch.cuda.synchronize()
         cms = (time.perf_counter() - c0) / 3
         result["hbm_copy_gbs"] = round(2 * z.numel() * 8 / cms / 1e9, 1)
-        # and for reading alone (a library reduction over the first 8 GiB of the input):
+        # the same from the library's own streaming probes (read only, write only, copy): reading alone is
         # the ceiling for phase 1, which writes next to nothing
-        zr = torch.view_as_real(z).reshape(-1)[: 1 << 31]
-        rsec = timed(torch, lambda: zr.sum(), 5)
-        result["hbm_read_gbs"] = round(zr.numel() * 4 / rsec / 1e9, 1)
+        for name, mode in (("hbm_read_gbs", 0), ("hbm_write_gbs", 1), ("hbm_probe_copy_gbs", 2)):
+            psec = timed(torch, lambda: g.probe_bandwidth(z, out, mode), 3)
+            result[name] = round((2 if mode == 2 else 1) * z.numel() * 8 / psec / 1e9, 1)
         # what the float matrix units sustain on this machine for a plain library GEMM (8192^3, float32)
         ga = torch.randn((8192, 8192), device=dev)
         gb = torch.randn((8192, 8192), device=dev)

@@ -104,6 +104,16 @@ int goom_profile_enable(goom_ctx *ctx, int enable);
 int goom_profile_count(const goom_ctx *ctx);
 int goom_profile_get(goom_ctx *ctx, int i, const char **label, float *milliseconds);
 
+/* What this device's memory system sustains for plain streaming, for setting a kernel's achieved
+ * rate beside something measured (measurement aid, not part of the method).  Enqueues one
+ * pass over `bytes` bytes (a multiple of 16; a, b 16-byte aligned device buffers of that size):
+ * GOOM_PROBE_READ reads a (b receives 4 bytes), GOOM_PROBE_WRITE fills b, GOOM_PROBE_COPY copies
+ * a to b.  The caller times it on the context's stream. */
+#define GOOM_PROBE_READ 0
+#define GOOM_PROBE_WRITE 1
+#define GOOM_PROBE_COPY 2
+int goom_probe_bandwidth(goom_ctx *ctx, const void *a, void *b, size_t bytes, int mode);
+
 /* ---- codecs (paper Section 3.1) -------------------------------------------------- */
 
 /* Real floats -> GOOMs: y[i] = (log|x[i]|, x[i] < 0 ? pi : 0).  x: n floats (GOOM_C64)

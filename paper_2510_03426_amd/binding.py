@@ -22,7 +22,7 @@ AFFINE_TIME_INVARIANT = 1
 
 EXPORTS = [
     "goom_version", "goom_create", "goom_destroy", "goom_set_stream", "goom_last_error",
-    "goom_status_name", "goom_profile_enable", "goom_profile_count", "goom_profile_get", "goom_to_goom", "goom_from_goom", "goom_lmme", "goom_lmme_workspace_bytes",
+    "goom_status_name", "goom_probe_bandwidth", "goom_profile_enable", "goom_profile_count", "goom_profile_get", "goom_to_goom", "goom_from_goom", "goom_lmme", "goom_lmme_workspace_bytes",
     "goom_scan", "goom_scan_workspace_bytes", "goom_reduce", "goom_reduce_workspace_bytes",
     "goom_scan_reset", "goom_scan_reset_workspace_bytes", "goom_lyapunov_spectrum",
     "goom_lyapunov_spectrum_per_step", "goom_lyapunov_spectrum_per_step_workspace_bytes",
@@ -99,6 +99,7 @@ def load_library():
     lib.goom_affine_scan.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
     lib.goom_affine_scan_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_affine_scan_workspace_bytes.restype = sz
+    lib.goom_probe_bandwidth.argtypes = [vp, vp, vp, sz, i32]
     lib.goom_affine_scan_scaled.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
     lib.goom_affine_scan_scaled_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_affine_scan_scaled_workspace_bytes.restype = sz
@@ -170,6 +171,11 @@ class Goom:
     def set_stream(self, stream):
         self._stream = stream
         self._check(self.lib.goom_set_stream(self._ctx, C.c_void_p(stream.cuda_stream)))
+
+    def probe_bandwidth(self, a, b, mode: int):
+        """One streaming pass (0 read a, 1 fill b, 2 copy a to b) on the context's stream; the caller times it."""
+        nbytes = b.numel() * b.element_size()
+        self._check(self.lib.goom_probe_bandwidth(self._ctx, _ptr(a), _ptr(b), nbytes, mode))
 
     def profile_enable(self, on: bool = True):
         self._check(self.lib.goom_profile_enable(self._ctx, int(on)))

@@ -563,6 +563,16 @@ int goom_set_stream(goom_ctx *ctx, void *stream)
     return GOOM_OK;
 }
 
+int goom_probe_bandwidth(goom_ctx *ctx, const void *a, void *b, size_t bytes, int mode)
+{
+    if (mode != GOOM_PROBE_READ && mode != GOOM_PROBE_WRITE && mode != GOOM_PROBE_COPY) return fail(ctx, GOOM_EINVAL, "unknown probe mode %d", mode);
+    if (!b || (!a && mode != GOOM_PROBE_WRITE)) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    if (bytes == 0 || bytes % 16 != 0 || !aligned(b, 16) || (a && !aligned(a, 16)))
+        return fail(ctx, GOOM_EINVAL, "the probe wants 16-byte aligned buffers of a multiple of 16 bytes");
+    if (int s = need_ctx(ctx)) return s;
+    return launch_probe(ctx, a, b, bytes, mode);
+}
+
 int goom_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, uint32_t flags)
 {
     if (int s = check_common(ctx, dtype)) return s;

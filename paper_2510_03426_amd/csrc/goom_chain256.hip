@@ -75,8 +75,14 @@ __global__ __launch_bounds__(kThreads256, kSlabs == 1 ? 2 : 1) void chain256_ker
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, c = lane & 15;
-    const long long chain = blockIdx.x / a.halves;
-    const int half = (int)(blockIdx.x % a.halves);
+    // Workgroups are dealt to the eight XCDs in turn (each has its own L2).  The two halves of a chain
+    // read the same matrices at the same time, so they are numbered eight apart: same XCD, same L2.
+    long long chain = blockIdx.x / a.halves;
+    int half = (int)(blockIdx.x % a.halves);
+    if (a.halves == 2 && (gridDim.x & 15) == 0) {
+        chain = (long long)(blockIdx.x >> 4) * 8 + (blockIdx.x & 7);
+        half = (blockIdx.x >> 3) & 1;
+    }
     const long long item = chain / a.chunks, chunk = chain % a.chunks;
     const long long t0 = chunk * a.L;
     long long len = a.T - t0;

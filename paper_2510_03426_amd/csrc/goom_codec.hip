@@ -238,4 +238,41 @@ int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype)
     return check_hip(ctx, hipGetLastError(), "launch from_goom");
 }
 
+
+// ---- streaming probes: every workgroup walks a contiguous span, eight 16-byte accesses per thread in flight
+namespace {
+typedef float pf4 __attribute__((ext_vector_type(4)));
+template <int MODE> __global__ __launch_bounds__(256) void probe_kernel(const pf4 *__restrict__ a, pf4 *__restrict__ b, size_t n)
+{
+    const size_t per = (n + gridDim.x - 1) / gridDim.x;
+    const size_t lo = per * blockIdx.x;
+    size_t hi = lo + per;
+    if (hi > n) hi = n;
+    pf4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (size_t i = lo + threadIdx.x; i < hi; i += 8 * 256) {
+        pf4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = (MODE != 1 && i + u * 256 < hi) ? a[i + u * 256] : pf4{1.f, 2.f, 3.f, 4.f};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (MODE == 0) acc += v[u];
+            else if (i + u * 256 < hi) b[i + u * 256] = v[u];
+        }
+    }
+    if (MODE == 0 && acc[0] + acc[1] + acc[2] + acc[3] == 1.2345f) reinterpret_cast<float *>(b)[0] = 1.0f;
+}
+} // namespace
+
+int launch_probe(goom_ctx *ctx, const void *a, void *b, size_t bytes, int mode)
+{
+    const size_t n = bytes / 16;
+    const pf4 *pa = static_cast<const pf4 *>(a);
+    pf4 *pb = static_cast<pf4 *>(b);
+    const unsigned grid = 4096;
+    if (mode == 0) hipLaunchKernelGGL(probe_kernel<0>, dim3(grid), dim3(256), 0, ctx->stream, pa, pb, n);
+    else if (mode == 1) hipLaunchKernelGGL(probe_kernel<1>, dim3(grid), dim3(256), 0, ctx->stream, pa, pb, n);
+    else hipLaunchKernelGGL(probe_kernel<2>, dim3(grid), dim3(256), 0, ctx->stream, pa, pb, n);
+    return check_hip(ctx, hipGetLastError(), "launch probe_kernel");
+}
+
 } // namespace goom

@@ -130,6 +130,7 @@ int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long
 int launch_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, uint32_t flags);
 int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype);
 int launch_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, size_t n, int dtype);
+int launch_probe(goom_ctx *ctx, const void *a, void *b, size_t bytes, int mode);
 int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t nvec, int d, int dtype);
 
 } // namespace goom
