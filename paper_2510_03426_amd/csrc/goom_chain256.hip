@@ -35,6 +35,7 @@ struct Chain256Args {
     const float2 *M;     // [batch][T][d][d] GOOMs
     const float *nrow;   // [batch][T][256] row shifts
     long long T, L, chunks; // chain length, chunk length, chunks per batch item this launch covers
+    long long nchains;      // batch * chunks
     int d, m, halves, mp;   // state is d x m, m <= mp = 128 * halves
     const float *init_s;    // NULL (identity) or [chain][mp][256] transposed mantissas
     const double *init_e;   //                    [chain][mp] column exponents
@@ -79,10 +80,11 @@ __global__ __launch_bounds__(kThreads256, kSlabs == 1 ? 2 : 1) void chain256_ker
     // read the same matrices at the same time, so they are numbered eight apart: same XCD, same L2.
     long long chain = blockIdx.x / a.halves;
     int half = (int)(blockIdx.x % a.halves);
-    if (a.halves == 2 && (gridDim.x & 15) == 0) {
+    if (a.halves == 2) { // (the grid is padded to a multiple of 16 workgroups)
         chain = (long long)(blockIdx.x >> 4) * 8 + (blockIdx.x & 7);
         half = (blockIdx.x >> 3) & 1;
     }
+    if (chain >= a.nchains) return; // whole workgroup, before any barrier
     const long long item = chain / a.chunks, chunk = chain % a.chunks;
     const long long t0 = chunk * a.L;
     long long len = a.T - t0;
@@ -311,8 +313,10 @@ int launch_chain256(goom_ctx *ctx, const void *M, const float *nrow, long long T
     a.out_s = out_s;
     a.out_e = out_e;
     a.P = static_cast<float2 *>(P);
-    const long long grid = batch * chunks * a.halves;
+    a.nchains = batch * chunks;
+    long long grid = a.nchains * a.halves;
     if (grid <= 0) return GOOM_OK;
+    if (a.halves == 2) grid = (grid + 15) / 16 * 16;
     if (grid > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many chains for one launch");
     const size_t lds = chain256_lds_bytes();
     if (int s = check_hip(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(chain256_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
