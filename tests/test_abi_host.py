@@ -80,6 +80,11 @@ def test_argument_validation_without_device(lib):
     assert lib.goom_affine_scan(None, p, p, None, None, 4, 8, 1, 0, None, None, 0) == EINVAL
     assert lib.goom_affine_scan_scaled(None, p, p, None, None, None, 4, 8, 1, 0, None, None, 0) == EINVAL
     assert lib.goom_affine_scan_scaled(None, p, p, None, p, None, 4, 8, 1, 0, None, None, 0) == EWS
+    # probes
+    assert lib.goom_probe_bandwidth(None, p, p, 1 << 20, 7) == EINVAL
+    assert lib.goom_probe_bandwidth(None, p, p, 100, 0) == EINVAL
+    assert lib.goom_probe_bandwidth(None, None, p, 1 << 20, 0) == EINVAL
+    assert lib.goom_probe_bandwidth(None, None, p, 1 << 20, 1) == EINVAL and "context" in err(lib)
     # context
     assert lib.goom_create(None, 0, None) == EINVAL
     ctx = C.c_void_p()

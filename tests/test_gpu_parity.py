@@ -742,6 +742,21 @@ def test_caller_stream_and_profile_records(G, oracle):
     assert any("phase1" in l for l in labels) and any("phase3" in l for l in labels) and all(ms >= 0 for _, ms in recs)
 
 
+def test_streaming_probes(G, oracle):
+    # the measurement aid: copy copies, fill fills, read leaves the data alone (ragged size, not a multiple of the grid)
+    import torch
+    n = (1 << 20) + 4 * 37
+    a = torch.arange(n, dtype=torch.float32, device="cuda")
+    b = torch.zeros_like(a)
+    G.probe_bandwidth(a, b, 2)
+    assert torch.equal(a, b)
+    G.probe_bandwidth(a, b, 1)
+    assert torch.equal(b.view(-1, 4), torch.tensor([1.0, 2.0, 3.0, 4.0], device="cuda").expand(n // 4, 4))
+    keep = b.clone()
+    G.probe_bandwidth(a, b, 0)
+    assert torch.equal(b, keep) and torch.equal(a, torch.arange(n, dtype=torch.float32, device="cuda"))
+
+
 # ------------------------------------------------------------------ degenerate cases of the method
 
 @pytest.mark.parametrize("d", [1, 3, 16, 64, 200])
