@@ -15,10 +15,74 @@ constexpr float kPiF = 3.14159274101257324219f;
 constexpr double kPiD = 3.14159265358979311600;
 constexpr double kInvPi = 0.318309886183790671538;
 
+// ln|x| in double for a finite non-zero x: x = m 2^k with m in [sqrt(1/2), sqrt(2)), ln m = 2 atanh(s),
+// s = (m - 1) / (m + 1), |s| < 0.1716, as its series to s^21 (remainder below 1e-17 relative; near x = 1
+// the result is the series alone, so it keeps its relative accuracy there).  About a third of the
+// instructions of the library routine, which made the float encoder compute bound.
+__device__ inline double ln_abs_f64(double x)
+{
+    int k;
+    double m = __builtin_frexp(__builtin_fabs(x), &k); // [1/2, 1)
+    const bool low = m < 0.70710678118654752440;
+    m = low ? m + m : m;
+    k = low ? k - 1 : k;
+    const double den = m + 1.0;
+    double r = (double)__builtin_amdgcn_rcpf((float)den);
+    r = r * (2.0 - den * r);
+    r = r * (2.0 - den * r);
+    const double num = m - 1.0;
+    double s = num * r;
+    s = __builtin_fma(__builtin_fma(-s, den, num), r, s); // s = num / den to rounding
+    const double z = s * s;
+    double p = 1.0 / 21.0;
+    p = __builtin_fma(p, z, 1.0 / 19.0);
+    p = __builtin_fma(p, z, 1.0 / 17.0);
+    p = __builtin_fma(p, z, 1.0 / 15.0);
+    p = __builtin_fma(p, z, 1.0 / 13.0);
+    p = __builtin_fma(p, z, 1.0 / 11.0);
+    p = __builtin_fma(p, z, 1.0 / 9.0);
+    p = __builtin_fma(p, z, 1.0 / 7.0);
+    p = __builtin_fma(p, z, 1.0 / 5.0);
+    p = __builtin_fma(p, z, 1.0 / 3.0);
+    p = __builtin_fma(p, z * s, s); // s + s^3 (1/3 + ...)
+    // k ln 2 with ln 2 in two parts: the high part has 32 significant bits, so k times it is exact
+    const double kLn2Hi = 0.693147180369123816490, kLn2Lo = 1.90821492927058770002e-10;
+    return __builtin_fma((double)k, kLn2Hi, __builtin_fma((double)k, kLn2Lo, p + p));
+}
+
+// e^x in double for a float x: k = round(x / ln 2), r = x - k ln 2 with ln 2 in two parts (exact for
+// such x), e^r as its series to r^13 (|r| < 0.35: remainder below 1e-17), scaled by 2^k.
+__device__ inline double exp_of_f32(float xf)
+{
+    const double x = (double)xf;
+    if (!(x > -800.0)) return x == x ? 0.0 : x;              // -inf and everything that underflows even in double; NaN stays
+    if (!(x < 800.0)) return __builtin_huge_val();            // overflows float by far
+    const double k = __builtin_rint(x * 1.44269504088896340736);
+    const double kLn2Hi = 0.693147180369123816490, kLn2Lo = 1.90821492927058770002e-10;
+    const double r = __builtin_fma(-k, kLn2Lo, __builtin_fma(-k, kLn2Hi, x));
+    double p = 1.0 / 6227020800.0;
+    p = __builtin_fma(p, r, 1.0 / 479001600.0);
+    p = __builtin_fma(p, r, 1.0 / 39916800.0);
+    p = __builtin_fma(p, r, 1.0 / 3628800.0);
+    p = __builtin_fma(p, r, 1.0 / 362880.0);
+    p = __builtin_fma(p, r, 1.0 / 40320.0);
+    p = __builtin_fma(p, r, 1.0 / 5040.0);
+    p = __builtin_fma(p, r, 1.0 / 720.0);
+    p = __builtin_fma(p, r, 1.0 / 120.0);
+    p = __builtin_fma(p, r, 1.0 / 24.0);
+    p = __builtin_fma(p, r, 1.0 / 6.0);
+    p = __builtin_fma(p, r, 0.5);
+    p = __builtin_fma(p, r, 1.0);
+    p = __builtin_fma(p, r, 1.0);
+    return __builtin_ldexp(p, (int)k);
+}
+
 __device__ inline float enc_re_f32(float v, bool zero_floor)
 {
     if (v == 0.0f) return zero_floor ? (float)kFloorF32 : -__builtin_huge_valf();
-    return (float)log((double)__builtin_fabsf(v));
+    const float av = __builtin_fabsf(v);
+    if (!(av < __builtin_huge_valf())) return av; // infinities and NaN pass through
+    return (float)ln_abs_f64((double)av);
 }
 
 __global__ __launch_bounds__(256) void to_goom_f32_kernel(const float *__restrict__ x, float *__restrict__ y,
@@ -71,7 +135,7 @@ __global__ __launch_bounds__(256) void from_goom_f32_kernel(const float *__restr
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         float2 z = reinterpret_cast<const float2 *>(y)[i];
-        float mag = (float)exp((double)z.x);
+        float mag = (float)exp_of_f32(z.x);
         x[i] = odd_multiple_of_pi((double)z.y) ? -mag : mag;
     }
 }
