@@ -1,7 +1,8 @@
 // Codec kernels: real floats <-> GOOMs (paper Section 3.1).  Pure streaming: 4 or 8
 // bytes in and 8 or 16 bytes out per element (or the reverse), so HBM bandwidth binds;
 // the logarithm / exponential is evaluated in double and rounded once to the component
-// type, which costs nothing visible next to the memory traffic.
+// type.  For float components that evaluation is a short series of its own (the library's
+// double routines made these kernels compute bound).
 #include "goom_internal.h"
 
 namespace {
