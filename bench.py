@@ -234,6 +234,7 @@ def other_workloads(g, torch, dev, only=None):
     want = lambda name: only is None or only == name
     if want("tiny"):
         res["scan_T256_d8"] = tiny_scan(g, torch, dev, si)
+        res.update(small_scans(g, torch, dev, si))
     if want("scan128"):
         res.update(scan128(g, torch, dev, si))
     if want("lmme"):
@@ -251,6 +252,23 @@ def tiny_scan(g, torch, dev, si):
     # tiny scan (T = 256, d = 8): latency of one call
     zt = g.to_goom(torch.randn((256, 8, 8), device=dev, generator=si.device_generator(11, dev)))
     return {"us_per_scan": round(timed(torch, lambda: g.scan(zt), 50) * 1e6, 1)}
+
+
+def small_scans(g, torch, dev, si):
+    # long chains of the smallest matrices (T = 2^22 of 8 x 8 and 16 x 16): bound by HBM, if anything
+    res = {}
+    for d in (8, 16):
+        T = 1 << 22
+        z = g.to_goom(torch.randn((T, d, d), device=dev, generator=si.device_generator(251003426 * 10 + 80 + d, dev)))
+        out = torch.empty_like(z)
+        sec = timed(torch, lambda: g.scan(z, out=out), 5)
+        byts = 3 * z.numel() * 8  # read, read, write
+        res[f"scan_T{T}_d{d}"] = {"ms": round(sec * 1e3, 3), "products_per_s": round(T / sec, 1),
+                                  "hbm_gbs_algorithmic": round(byts / sec / 1e9, 1),
+                                  "pct_of_hbm_peak": round(100 * byts / sec / 1e9 / HBM_PEAK_GBS, 2),
+                                  "kernels_ms": kernel_times(g, lambda: g.scan(z, out=out))}
+        del z, out
+    return res
 
 
 def scan128(g, torch, dev, si):

@@ -4,6 +4,7 @@
 namespace goom_chain {
 int dispatch_f32_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label)
 {
+    if (small_applies(args)) return dispatch_small(ctx, args, grid, label);
     if (fast_applies(args, dp, nw)) return dispatch_fast(ctx, args, dp, grid, label);
     if (affine_chunk_applies(args, dp)) return dispatch_affine_chunk(ctx, args, dp, grid, label);
     if (affine_walk_applies(args, dp)) return dispatch_affine_walk(ctx, args, dp, grid, label);

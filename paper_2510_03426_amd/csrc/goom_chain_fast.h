@@ -428,6 +428,10 @@ int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long
 int launch_replicate_power(goom_ctx *ctx, void *totals, long long stride, int fact_cols, int dp, int d, long long batch,
                            long long chunks, long long chunks_per_item);
 
+// 8 x 8 and 16 x 16 chains: one wave per chain (or per pair of 8 x 8 chains), separate translation unit
+bool small_applies(const ChainArgs &args);
+int dispatch_small(goom_ctx *ctx, const ChainArgs &args, long long nchains, const char *label);
+
 inline int dispatch_fast(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label)
 {
     switch (dp) {
