@@ -262,6 +262,17 @@ def test_scan_sizes_and_ragged_tails(G, oracle, T, d, chunk):
     run_scan_case(G, oracle, T, d, chunk, name=f"T{T}d{d}")
 
 
+def test_scan_small_matrices_in_pairs(G, oracle):
+    # 8 x 8 chains share a wave two by two: pairs that straddle batch items, a ragged last chunk that is shorter
+    # than its partner, an odd number of chains, single steps; 16 x 16 chains one per wave
+    run_scan_case(G, oracle, 37, 8, 5, batch=3, seed=11, name="d8 batch3 ragged")     # 8 chunks per item, last of 2 steps
+    run_scan_case(G, oracle, 35, 8, 5, batch=3, seed=12, name="d8 batch3 odd chains")  # 7 chunks per item: 21 chains
+    run_scan_case(G, oracle, 1, 8, 0, batch=5, seed=13, name="d8 single step")
+    run_scan_case(G, oracle, 1200, 8, 0, seed=14, name="d8 default chunks")
+    run_scan_case(G, oracle, 41, 16, 6, batch=2, seed=15, name="d16 batch2 ragged")
+    run_scan_case(G, oracle, 1000, 8, 3, seed=16, name="d8 334 chunks grouped carries")
+
+
 def test_scan_many_chunks_grouped_carries(G, oracle):
     # more than 96 chunks: the carry phase is itself a grouped scan (group products, their
     # prefixes, groups re-walked); ragged last chunk and ragged last group
