@@ -114,6 +114,64 @@ def test_config2_long_chain_scan_full_size(G, oracle):
     del z, out
 
 
+@pytest.mark.parametrize("d,tmax", [(8, 1 << 21), (16, 1 << 20)])
+def test_long_scans_of_small_matrices(G, oracle, d, tmax):
+    # T = 2^22 chains of 8 x 8 and 16 x 16 matrices, as the benchmark runs them (8192 chunks of 512 steps, one
+    # wave per chain or per pair of 8 x 8 chains): the leading part against the oracle, the one-step recurrence
+    # at 600 chunk boundaries and interior steps below tmax (further on a stored log-magnitude is so coarsely
+    # rounded that the check says little), the reduction, the growth rate
+    import torch
+    T = 1 << 22
+    L = 512
+    device = torch.device("cuda", 0)
+    keep = 32768
+    z = torch.empty((T, d, d), dtype=torch.complex64, device=device)
+    rng = np.random.default_rng(70 + d)
+    sampled = sorted(set(int(v) * L for v in rng.integers(1, tmax // L, 500)) | set(int(v) for v in rng.integers(1, tmax, 100)) | {L, 2 * L})
+    x_keep = {}
+    x_head = None
+    say(f"long scan of small matrices: T={T} d={d}")
+    blk = 1 << 19
+    for t0, x in si.device_normal_blocks(si.BASE_SEED * 10 + 80 + d, T, (d, d), device, blk):
+        G.to_goom(x, out=z[t0:t0 + x.shape[0]])
+        if t0 == 0:
+            x_head = x[:keep].cpu().numpy()
+        xs_host = None
+        for t in sampled:
+            if t0 <= t < t0 + x.shape[0]:
+                if xs_host is None:
+                    xs_host = x.cpu().numpy()
+                x_keep[t] = xs_host[t - t0]
+        del x
+    out = G.scan(z)
+    torch.cuda.synchronize()
+    zs = host(z[:keep])
+    assert np.array_equal(zs.view(np.uint32), oracle.to_goom(x_head).view(np.uint32))
+    sample = sorted({0, 1, 2, 3, 4, 5, L - 1, L, L + 1, 2 * L - 1, 2 * L, 17 * L, keep - 1} | set(range(499, keep, 997)))
+    fn = lambda mats: oracle.ScanStream(d, scaled=True).advance(mats, sample_t=sample, return_kappa=True)
+    re, sg, kap, well = with_sensitivity(fn, [zs], np.float32, nprobe=1)
+    compare(host(out[sample]), re, sg, kap, name=f"d={d}: {len(sample)} sampled prefixes of the first {keep}", max_ill_fraction=0.03, well=well)
+    worst, bad_signs = 0.0, 0
+    idx = torch.tensor(sampled, device=device)
+    cur_all, prev_all = host(out[idx]), host(out[idx - 1])
+    for n, t in enumerate(sampled):
+        defect, signs, frac = one_step_defect(x_keep[t], prev_all[n], cur_all[n])
+        worst = max(worst, defect)
+        bad_signs += signs
+    say(f"  one-step recurrence at {len(sampled)} steps: worst defect {worst:.3f}, {bad_signs} sign mismatches")
+    assert worst < 0.75 and bad_signs == 0
+    fin = host(G.reduce(z))
+    last = host(out[T - 1])
+    dre = np.abs(fin.real.astype(np.float64) - last.real.astype(np.float64))
+    assert np.array_equal(fin.imag, last.imag) and np.all(dre <= tolerance(last.real.astype(np.float64), np.float32))
+    from scipy.special import digamma
+    lam = 0.5 * (math.log(2.0) + digamma(d / 2))
+    rate = float(last.real.max()) / T
+    say(f"  log-magnitude of the last prefix: {last.real.max():.1f}; growth per step {rate:.5f} (closed form {lam:.5f})")
+    assert abs(rate - lam) < 1.5e-3
+    del z, out
+
+
 @pytest.mark.parametrize("ctype", ["complex64", "complex128"])
 def test_config3_batched_lmme_full_size(G, oracle, ctype):
     import torch
