@@ -141,7 +141,7 @@ def long_scan_case(G, oracle, T, d, L, keep, tmax, nbound, blk, seed, rate_tol):
     torch.cuda.synchronize()
     zs = host(z[:keep])
     assert np.array_equal(zs.view(np.uint32), oracle.to_goom(x_head).view(np.uint32))
-    sample = sorted(t for t in ({0, 1, 2, 3, L - 1, L, L + 1, 2 * L - 1, 2 * L, 3 * L, keep - 1} | set(range(keep // 7, keep, keep // 9))) if t < keep)
+    sample = sorted(t for t in ({0, 1, 2, 3, L - 1, L, L + 1, 2 * L - 1, 2 * L, 3 * L, keep - 1} | (set(range(keep // 7, keep, keep // 9)) if keep >= 9 else set())) if t < keep)
     fn = lambda mats: oracle.ScanStream(d, scaled=True).advance(mats, sample_t=sample, return_kappa=True)
     re, sg, kap, well = with_sensitivity(fn, [zs], np.float32, nprobe=1)
     compare(host(out[sample]), re, sg, kap, name=f"d={d}: {len(sample)} sampled prefixes of the first {keep}", max_ill_fraction=0.03, well=well)
@@ -179,6 +179,12 @@ def test_long_scans_of_small_matrices(G, oracle, d, tmax):
 def test_long_scan_128(G, oracle):
     # T = 2^18 chain of 128 x 128 matrices (256 chunks of 1024 steps, one workgroup per compute unit)
     long_scan_case(G, oracle, 1 << 18, 128, 1024, 2048, 1 << 18, 300, 1 << 14, 128, 2e-3)
+
+
+def test_long_scan_1024(G, oracle):
+    # T = 512 chain of 1024 x 1024 matrices (8 chunks of 64 steps, every step a round of GEMM launches); the
+    # oracle walks the first steps only, the recurrence is checked at every chunk boundary
+    long_scan_case(G, oracle, 512, 1024, 64, 3, 512, 10, 64, 1024, 2e-2)
 
 
 def test_long_scan_256(G, oracle):
