@@ -155,6 +155,20 @@ def main():
         rms = (time.perf_counter() - r0) / 3 * 1e3
         result["reduce"] = {"ms": round(rms, 4), "products_per_s": round(T / (rms * 1e-3), 1),
                             "hbm_gbs": round(T * 8 * d * d / (rms * 1e-3) / 1e9, 1)}
+    if not args.no_extras and not args.basic_extras and d in (32, 64, 128):
+        # the same scan fed with the real matrices themselves (4 bytes per entry in instead of 8; an extra of
+        # the library, not the configuration `value` is quoted on)
+        gen.manual_seed(251003426 * 10 + 2)
+        xr = torch.empty((T, d, d), dtype=torch.float32, device=dev)
+        for t0 in range(0, T, blk):
+            t1 = min(T, t0 + blk)
+            xr[t0:t1] = torch.randn((t1 - t0, d, d), dtype=torch.float32, device=dev, generator=gen)
+        xsec = timed(torch, lambda: g.scan_real(xr, chunk_len=args.chunk_len, out=out), 3)
+        result["scan_of_real_matrices"] = {"ms": round(xsec * 1e3, 4), "products_per_s": round(T / xsec, 1),
+                                           "lmme_tflops_executed": round(2.0 * d ** 3 * 2 * T / xsec / 1e12, 2),
+                                           "pct_of_fp32_mfma_peak": round(100 * 2.0 * d ** 3 * 2 * T / xsec / 1e12 / MFMA_F32_PEAK_TFLOPS, 2),
+                                           "kernels_ms": kernel_times(g, lambda: g.scan_real(xr, chunk_len=args.chunk_len, out=out))}
+        del xr
     if not args.no_extras:
         result["to_goom_gbs"] = round(z.numel() * 12 / t_codec / 1e9, 1)
         # the decoder on the first 2^28 inputs (log-magnitudes of N(0,1) draws, all inside float range)

@@ -171,6 +171,25 @@ int goom_reduce(goom_ctx *ctx, const void *M, const void *init, void *P_final, i
 size_t goom_reduce_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype,
                                    const goom_scan_opts *opts);
 
+/* The same scan and reduction over REAL matrices X: [batch, T, d, d] of the component type (floats for
+ * GOOM_C64), i.e. goom_scan(goom_to_goom(X)) without the encoded copy of the input: chains usually start
+ * from real matrices (paper Section 4.1 draws them from N(0, 1)), and reading them directly halves the
+ * input traffic.  For GOOM_C64 with d = 32, 64 or 128 and a square state the chain kernel reads the reals
+ * itself and scales an entry by its powers of two exactly (no logarithm or exponential on the way in, so
+ * the result is that of the scan over exactly encoded inputs); other shapes are encoded into the
+ * workspace first.  init, P, opts as for goom_scan.  workspace: goom_scan_real_workspace_bytes(...) /
+ * goom_reduce_real_workspace_bytes(...) bytes. */
+int goom_scan_real(goom_ctx *ctx, const void *X, const void *init, void *P, int64_t T, int d, int m,
+                   int64_t batch, int dtype, const goom_scan_opts *opts, void *workspace,
+                   size_t workspace_bytes);
+size_t goom_scan_real_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype,
+                                      const goom_scan_opts *opts);
+int goom_reduce_real(goom_ctx *ctx, const void *X, const void *init, void *P_final, int64_t T, int d,
+                     int m, int64_t batch, int dtype, const goom_scan_opts *opts, void *workspace,
+                     size_t workspace_bytes);
+size_t goom_reduce_real_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype,
+                                        const goom_scan_opts *opts);
+
 /* ---- selectively reset scan and Lyapunov spectrum (paper Section 5; Section 4.2.1) - */
 
 #define GOOM_RESET_ALWAYS 1     /* reset at every examined state */

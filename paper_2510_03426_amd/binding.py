@@ -24,6 +24,7 @@ EXPORTS = [
     "goom_version", "goom_create", "goom_destroy", "goom_set_stream", "goom_last_error",
     "goom_status_name", "goom_probe_bandwidth", "goom_profile_enable", "goom_profile_count", "goom_profile_get", "goom_to_goom", "goom_from_goom", "goom_lmme", "goom_lmme_workspace_bytes",
     "goom_scan", "goom_scan_workspace_bytes", "goom_reduce", "goom_reduce_workspace_bytes",
+    "goom_scan_real", "goom_scan_real_workspace_bytes", "goom_reduce_real", "goom_reduce_real_workspace_bytes",
     "goom_scan_reset", "goom_scan_reset_workspace_bytes", "goom_lyapunov_spectrum",
     "goom_lyapunov_spectrum_per_step", "goom_lyapunov_spectrum_per_step_workspace_bytes",
     "goom_largest_lyapunov", "goom_largest_lyapunov_workspace_bytes",
@@ -83,6 +84,12 @@ def load_library():
     lib.goom_reduce.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i32, po, vp, sz]
     lib.goom_reduce_workspace_bytes.argtypes = [i64, i32, i32, i64, i32, po]
     lib.goom_reduce_workspace_bytes.restype = sz
+    lib.goom_scan_real.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i32, po, vp, sz]
+    lib.goom_scan_real_workspace_bytes.argtypes = [i64, i32, i32, i64, i32, po]
+    lib.goom_scan_real_workspace_bytes.restype = sz
+    lib.goom_reduce_real.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i32, po, vp, sz]
+    lib.goom_reduce_real_workspace_bytes.argtypes = [i64, i32, i32, i64, i32, po]
+    lib.goom_reduce_real_workspace_bytes.restype = sz
     pr = C.POINTER(ResetOpts)
     lib.goom_scan_reset.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, pr, vp, sz]
     lib.goom_scan_reset_workspace_bytes.argtypes = [i64, i32, i64, i32, pr]
@@ -268,6 +275,30 @@ class Goom:
         ws, wsn = self.workspace(self.lib.goom_reduce_workspace_bytes(T, d, m, batch, code, C.byref(opts)))
         self._check(self.lib.goom_reduce(self._ctx, _ptr(mats), _ptr(init), _ptr(out), T, d, m, batch, code,
                                          C.byref(opts), _ptr(ws), wsn))
+        return out
+
+    def scan_real(self, x, init=None, chunk_len: int = 0, out=None, final_only: bool = False):
+        """Prefix products (or, with final_only, the last one) of real matrices x: [..., T, d, d], as GOOMs."""
+        torch = self.torch
+        ctype = torch.complex64 if x.dtype == torch.float32 else torch.complex128
+        code = C64 if x.dtype == torch.float32 else C128
+        T, d = x.shape[-3], x.shape[-1]
+        lead = x.shape[:-3]
+        m = d if init is None else init.shape[-1]
+        batch = 1
+        for s in lead:
+            batch *= s
+        opts = ScanOpts(chunk_len, 0)
+        if out is None:
+            out = torch.empty(lead + ((d, m) if final_only else (T, d, m)), dtype=ctype, device=x.device)
+        if final_only:
+            ws, wsn = self.workspace(self.lib.goom_reduce_real_workspace_bytes(T, d, m, batch, code, C.byref(opts)))
+            self._check(self.lib.goom_reduce_real(self._ctx, _ptr(x), _ptr(init), _ptr(out), T, d, m, batch, code,
+                                                  C.byref(opts), _ptr(ws), wsn))
+        else:
+            ws, wsn = self.workspace(self.lib.goom_scan_real_workspace_bytes(T, d, m, batch, code, C.byref(opts)))
+            self._check(self.lib.goom_scan_real(self._ctx, _ptr(x), _ptr(init), _ptr(out), T, d, m, batch, code,
+                                                C.byref(opts), _ptr(ws), wsn))
         return out
 
     def affine_scan(self, a, bias, h0=None, chunk_len: int = 0, out=None, time_invariant: bool = False):

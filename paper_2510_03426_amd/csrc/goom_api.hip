@@ -286,7 +286,7 @@ static int carry_phase(goom_ctx *ctx, const ScanPlan &p, int dtype, int d, long 
 
 // scan and reduce share one driver; `final_only` selects the reduction
 static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, long long T, int d, int m, long long batch,
-                    int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes, bool final_only)
+                    int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes, bool final_only, bool left_real = false)
 {
     if (int s = check_scan_args(ctx, M, P, T, d, m, batch, dtype, opts, GOOM_MAX_DIM_LMME)) return s;
     if (!init && m != d) return fail(ctx, GOOM_EINVAL, "without an initial state the outputs are d x d (m=%d d=%d)", m, d);
@@ -310,8 +310,10 @@ static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, lon
     base.d = d;
     base.batch = batch;
     base.left = M;
-    base.left_batch_stride = (long long)T * d * d * cb;
-    base.left_step_stride = (long long)d * d * cb;
+    base.left_real = left_real ? 1 : 0;
+    const size_t cbl = left_real ? comp_bytes(dtype) : cb; // bytes per entry of a left factor
+    base.left_batch_stride = (long long)T * d * d * cbl;
+    base.left_step_stride = (long long)d * d * cbl;
     base.steps = T;
 
     if (p.C == 1) { // one chain per batch item walks everything
@@ -691,6 +693,55 @@ int goom_reduce(goom_ctx *ctx, const void *M, const void *init, void *P_final, i
                 int dtype, const goom_scan_opts *opts, void *workspace, size_t workspace_bytes)
 {
     return run_scan(ctx, M, init, P_final, T, d, m, batch, dtype, opts, workspace, workspace_bytes, true);
+}
+
+// Scans of real matrices: the hot float kernel reads them directly where it applies; elsewhere they are
+// encoded into the workspace first.
+static bool real_input_native(int d, int m, int dtype) { return dtype == GOOM_C64 && m == d && (d == 32 || d == 64 || d == 128); }
+
+static size_t real_scan_workspace(int64_t T, int d, int m, int64_t batch, int dtype, const goom_scan_opts *opts, bool final_only)
+{
+    const size_t base = final_only ? goom_reduce_workspace_bytes(T, d, m, batch, dtype, opts) : goom_scan_workspace_bytes(T, d, m, batch, dtype, opts);
+    if (T <= 0 || d <= 0 || m <= 0 || batch <= 0 || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
+    if (real_input_native(d, m, dtype)) return base;
+    return align_up(base, 256) + align_up((size_t)batch * (size_t)T * d * d * 2 * comp_bytes(dtype), 256);
+}
+
+static int run_scan_real(goom_ctx *ctx, const void *X, const void *init, void *P, long long T, int d, int m, long long batch, int dtype,
+                         const goom_scan_opts *opts, void *ws, size_t ws_bytes, bool final_only)
+{
+    if (int s = check_scan_args(ctx, X, P, T, d, m, batch, dtype, opts, GOOM_MAX_DIM_LMME)) return s;
+    if (real_input_native(d, m, dtype)) return run_scan(ctx, X, init, P, T, d, m, batch, dtype, opts, ws, ws_bytes, final_only, true);
+    const size_t base = final_only ? goom_reduce_workspace_bytes(T, d, m, batch, dtype, opts) : goom_scan_workspace_bytes(T, d, m, batch, dtype, opts);
+    const size_t zoff = align_up(base, 256);
+    const size_t need = zoff + align_up((size_t)batch * (size_t)T * d * d * 2 * comp_bytes(dtype), 256);
+    if (int s = check_workspace(ctx, ws, ws_bytes, need)) return s;
+    if (int s = need_ctx(ctx)) return s;
+    void *Z = static_cast<unsigned char *>(ws) + zoff;
+    if (int s = launch_to_goom(ctx, X, Z, (size_t)batch * (size_t)T * d * d, dtype, 0)) return s;
+    return run_scan(ctx, Z, init, P, T, d, m, batch, dtype, opts, base ? ws : nullptr, base, final_only, false);
+}
+
+size_t goom_scan_real_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype, const goom_scan_opts *opts)
+{
+    return real_scan_workspace(T, d, m, batch, dtype, opts, false);
+}
+
+size_t goom_reduce_real_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype, const goom_scan_opts *opts)
+{
+    return real_scan_workspace(T, d, m, batch, dtype, opts, true);
+}
+
+int goom_scan_real(goom_ctx *ctx, const void *X, const void *init, void *P, int64_t T, int d, int m, int64_t batch, int dtype,
+                   const goom_scan_opts *opts, void *workspace, size_t workspace_bytes)
+{
+    return run_scan_real(ctx, X, init, P, T, d, m, batch, dtype, opts, workspace, workspace_bytes, false);
+}
+
+int goom_reduce_real(goom_ctx *ctx, const void *X, const void *init, void *P_final, int64_t T, int d, int m, int64_t batch, int dtype,
+                     const goom_scan_opts *opts, void *workspace, size_t workspace_bytes)
+{
+    return run_scan_real(ctx, X, init, P_final, T, d, m, batch, dtype, opts, workspace, workspace_bytes, true);
 }
 
 size_t goom_affine_scan_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts)

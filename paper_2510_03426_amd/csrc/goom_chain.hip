@@ -63,11 +63,14 @@ int launch_chain(goom_ctx *ctx, const ChainLaunch &l)
     a.bias_mode = l.bias_mode;
     a.bias_col = l.bias_col;
     a.bias = static_cast<const unsigned char *>(l.bias);
+    a.left_real = l.left_real;
     a.out_scaled = static_cast<float *>(l.out_scaled);
     a.out_logscale = static_cast<float *>(l.out_logscale);
     if (a.out_scaled && (l.dtype != GOOM_C64 || l.left_fact))
         return fail(ctx, GOOM_EUNSUPPORTED, "scaled outputs are written by the float matrix-vector walk only");
     const long long grid = l.batch * l.chunks_launched;
+    if (l.left_real && (l.dtype != GOOM_C64 || l.left_fact))
+        return fail(ctx, GOOM_EUNSUPPORTED, "real left factors are read by the hot float kernel only");
     if (l.dtype == GOOM_C64)
         return l.left_fact ? goom_chain::dispatch_f32_fact(ctx, a, dp, nw, grid, l.label) : goom_chain::dispatch_f32_goom(ctx, a, dp, nw, grid, l.label);
     return l.left_fact ? goom_chain::dispatch_f64_fact(ctx, a, dp, nw, grid, l.label) : goom_chain::dispatch_f64_goom(ctx, a, dp, nw, grid, l.label);

@@ -43,9 +43,9 @@ template <int CTRL> __device__ inline float add_dpp(float x)
     return x + __builtin_bit_cast(float, y);
 }
 
-template <int DP, int NW, bool BIAS>
-// (second launch bound: waves per SIMD the register allocation has to leave room for)
-__global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 16 ? 8 : DP == 32 ? (BIAS ? 5 : 6) : DP == 64 ? (BIAS ? 3 : 4) : 2)) void chain_kernel_fast(ChainArgs a)
+// REAL: the left factors are plain real matrices (4 bytes per entry instead of a GOOM's 8): an entry is
+// scaled by 2^(r_j - n_i) exactly, with no logarithm or exponential on the way in.
+template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void chain_body(const ChainArgs &a)
 {
     typedef Comp<float> C;
     constexpr int KT = DP / 16;
@@ -96,9 +96,13 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 16 ? 8 : DP == 3
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             const int row = (tid + q * NT) / LPR;
-            const f4 *gp = reinterpret_cast<const f4 *>(src + ((size_t)row * DP + c4) * 2);
-            it[q].a = gp[0];
-            it[q].b = gp[1];
+            if (REAL) {
+                it[q].a = *reinterpret_cast<const f4 *>(src + (size_t)row * DP + c4);
+            } else {
+                const f4 *gp = reinterpret_cast<const f4 *>(src + ((size_t)row * DP + c4) * 2);
+                it[q].a = gp[0];
+                it[q].b = gp[1];
+            }
         }
     };
 
@@ -114,6 +118,31 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 16 ? 8 : DP == 3
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             const int row = (tid + q * NT) / LPR;
+            if (REAL) {
+                // binary exponents (frexp convention) take the place of the log2 magnitudes; all shifts are exact
+                float ex[4];
+                float u = -3.0e38f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    ex[e] = C::exponent_of(it[q].a[e]) + rj[e];
+                    u = vmax_raw(u, it[q].a[e] != 0.0f ? ex[e] : -3.0e38f);
+                }
+                int key = C::key_of(u);
+                key = C::imax(key, C::dpp<0xB1>(key));
+                if (LPR >= 4) key = C::imax(key, C::dpp<0x4E>(key));
+                if (LPR >= 8) key = C::imax(key, C::dpp<0x141>(key));
+                if (LPR >= 16) key = C::imax(key, C::dpp<0x140>(key));
+                if (LPR >= 32) key = C::xor16_imax(key);
+                const float mx = C::of_key(key);
+                const bool zero_row = !(mx > -1.0e30f);
+                const float n = zero_row ? (BIAS ? 0.0f : -1.0e30f) : mx;
+                f4 y;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) y[e] = zero_row ? 0.0f : __builtin_ldexpf(it[q].a[e], (int)C::clamp_shift(rj[e] - n));
+                *reinterpret_cast<f4 *>(&tile[row * LDA + c4]) = y;
+                nsh[row] = n;
+                continue;
+            }
             const float re[4] = {it[q].a[0], it[q].a[2], it[q].b[0], it[q].b[2]};
             const float im[4] = {it[q].a[1], it[q].a[3], it[q].b[1], it[q].b[3]};
             // row maximum of log2|A_ij| + r_j, to within rounding (any nearby whole number serves)
@@ -393,11 +422,26 @@ __global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 16 ? 8 : DP == 3
     }
 }
 
-template <int DP, int NW, bool BIAS> int launch_fast(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
+// (second launch bound: waves per SIMD the register allocation has to leave room for)
+template <int DP, int NW, bool BIAS>
+__global__ __launch_bounds__((NW + (BIAS ? 1 : 0)) * 64, (DP <= 16 ? 8 : DP == 32 ? (BIAS ? 5 : 6) : DP == 64 ? (BIAS ? 3 : 4) : 2)) void chain_kernel_fast(ChainArgs a)
+{
+    chain_body<DP, NW, BIAS, false>(a);
+}
+
+template <int DP, int NW>
+__global__ __launch_bounds__(NW * 64, (DP <= 16 ? 8 : DP == 32 ? 6 : DP == 64 ? 4 : 2)) void chain_kernel_fast_real(ChainArgs a)
+{
+    chain_body<DP, NW, false, true>(a);
+}
+
+template <int DP, int NW, bool BIAS, bool REAL = false> int launch_fast(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
 {
     constexpr int LDA = DP + 4;
     const size_t lds = 2 * ((size_t)DP * LDA * sizeof(float) + (size_t)DP * sizeof(float)) + 128 + (BIAS ? DP * sizeof(float) : 0);
-    auto kern = chain_kernel_fast<DP, NW, BIAS>;
+    void (*kern)(ChainArgs);
+    if constexpr (REAL) kern = chain_kernel_fast_real<DP, NW>;
+    else kern = chain_kernel_fast<DP, NW, BIAS>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return goom::check_hip(ctx, e, "hipFuncSetAttribute(chain_kernel_fast)");
@@ -415,7 +459,8 @@ template <int DP, int NW, bool BIAS> int launch_fast(goom_ctx *ctx, const ChainA
 inline bool fast_applies(const ChainArgs &args, int dp, int nw)
 {
     return args.n == dp && args.d == dp && args.m == 16 * nw && args.bias_mode == 0 && args.out_fact_steps == nullptr &&
-           ((dp == 16 && nw == 1) || (dp == 32 && nw == 2) || (dp == 64 && nw == 4) || (dp == 128 && nw == 8));
+           ((dp == 16 && nw == 1) || (dp == 32 && nw == 2) || (dp == 64 && nw == 4) || (dp == 128 && nw == 8)) &&
+           (!args.left_real || dp >= 32);
 }
 
 // Kernels of the linear recurrence with bias (separate translation unit): chunk products of
@@ -434,6 +479,13 @@ int dispatch_small(goom_ctx *ctx, const ChainArgs &args, long long nchains, cons
 
 inline int dispatch_fast(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label)
 {
+    if (args.left_real) {
+        switch (dp) {
+        case 32: return launch_fast<32, 2, false, true>(ctx, args, grid, label);
+        case 64: return launch_fast<64, 4, false, true>(ctx, args, grid, label);
+        default: return launch_fast<128, 8, false, true>(ctx, args, grid, label);
+        }
+    }
     switch (dp) {
     case 16: return launch_fast<16, 1, false>(ctx, args, grid, label);
     case 32: return launch_fast<32, 2, false>(ctx, args, grid, label);

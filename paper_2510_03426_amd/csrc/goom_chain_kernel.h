@@ -55,6 +55,7 @@ struct ChainArgs {
     const unsigned char *bias;
     // linear recurrence with bias, matrix-vector walk only: states in scaled floating-point form
     // (paper eq. 21) instead of, or besides, GOOMs
+    int left_real;       // 1: the left factors are real matrices (component type), not GOOMs (hot float kernel only)
     float *out_scaled;   // NULL or [batch, steps, d]
     float *out_logscale; // NULL or [batch, steps]
 };

@@ -254,7 +254,7 @@ template <int D, bool OUT> int launch_small(goom_ctx *ctx, const ChainArgs &args
 bool small_applies(const ChainArgs &args)
 {
     return (args.d == 8 || args.d == 16) && args.n == args.d && args.m == args.d && args.bias_mode == 0 && args.out_fact_steps == nullptr &&
-           (args.init_mode == 0 || args.init_mode == 1) && !args.out_goom_last_only && args.out_scaled == nullptr &&
+           (args.init_mode == 0 || args.init_mode == 1) && !args.out_goom_last_only && args.out_scaled == nullptr && !args.left_real &&
            (args.out_goom != nullptr || args.out_fact_final != nullptr) && (args.out_fact_final == nullptr || args.fact_cols >= 16);
 }
 

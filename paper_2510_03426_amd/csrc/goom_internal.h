@@ -59,6 +59,7 @@ struct ChainLaunch {
     int d;                // columns of the left factors, rows of the state
     int m;                // columns of the state
     int left_fact;        // 0: left factors are GOOM matrices; 1: factored matrices (common exponent)
+    int left_real;        // 1 (with left_fact = 0): left factors are real matrices of the component type
     const void *left;     // first left factor of batch item 0
     long long left_batch_stride; // bytes
     long long left_step_stride;  // bytes

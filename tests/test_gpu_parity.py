@@ -273,6 +273,40 @@ def test_scan_small_matrices_in_pairs(G, oracle):
     run_scan_case(G, oracle, 1000, 8, 3, seed=16, name="d8 334 chunks grouped carries")
 
 
+@pytest.mark.parametrize("T,d,chunk,m,batch,comp", [(300, 64, 32, None, 1, np.float32), (130, 128, 16, None, 1, np.float32),
+                                                     (257, 32, 0, None, 2, np.float32), (90, 64, 0, 64, 2, np.float32),
+                                                     (1, 64, 0, None, 1, np.float32),
+                                                     (100, 16, 7, None, 2, np.float32), (60, 24, 9, 5, 1, np.float32),
+                                                     (40, 200, 8, None, 1, np.float32), (50, 32, 8, None, 1, np.float64)])
+def test_scan_of_real_matrices(G, oracle, T, d, chunk, m, batch, comp):
+    # the scan fed with real matrices (read directly by the hot kernel at d = 32, 64, 128; encoded into the
+    # workspace otherwise) against the oracle's scan of the encoded matrices
+    x = si.normal_f32(si.BASE_SEED + 90, 3, batch * T * d * d).reshape(batch, T, d, d).astype(comp)
+    if T > 3:
+        x[0, 2, 1, :] = 0.0   # a zero row
+        x[0, 3, :, 2] = 0.0   # a zero column
+    Z = oracle.to_goom(x)
+    init = None
+    if m is not None:
+        init = oracle.to_goom(si.normal_f32(si.BASE_SEED + 91, 4, batch * d * m).reshape(batch, d, m).astype(comp))
+    say(f"scan of reals T={T} d={d} chunk={chunk} m={m} batch={batch} {np.dtype(comp).name}")
+    out = host(G.scan_real(dev(x), None if init is None else dev(init), chunk_len=chunk))
+    red = host(G.scan_real(dev(x), None if init is None else dev(init), chunk_len=chunk, final_only=True))
+    big = d > 128
+    for b in range(batch):
+        if big:
+            sample = sorted({0, 1, T // 2, T - 1})
+            st = oracle.ScanStream(d, m=d if m is None else m, init=None if init is None else init[b], scaled=True)
+            re, sg, kap = st.advance(Z[b], sample_t=sample, return_kappa=True)
+            compare(out[b][sample], re, sg, kap, name=f"real scan d{d} item {b}", max_ill_fraction=0.06)
+            compare(red[b], re[-1], sg[-1], kap[-1], name=f"real reduce d{d} item {b}", max_ill_fraction=0.06)
+        else:
+            fn = lambda mats, ini: oracle.scan(mats, init=ini, return_kappa=True)
+            re, sg, kap, well = with_sensitivity(fn, [Z[b], None if init is None else init[b]], comp)
+            compare(out[b], re, sg, kap, name=f"real scan b{b}", max_ill_fraction=0.03, well=well)
+            compare(red[b], re[-1], sg[-1], kap[-1], name=f"real reduce b{b}", max_ill_fraction=0.06, well=well[-1])
+
+
 def test_scan_many_chunks_grouped_carries(G, oracle):
     # more than 96 chunks: the carry phase is itself a grouped scan (group products, their
     # prefixes, groups re-walked); ragged last chunk and ragged last group
