@@ -67,6 +67,10 @@ def test_argument_validation_without_device(lib):
     assert lib.goom_scan(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), C.c_void_p(0x1010), need) == EINVAL
     assert lib.goom_scan(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), p, need) == EINVAL and "context" in err(lib)
     assert lib.goom_reduce(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), None, 0) == EWS
+    # scans of real matrices
+    assert lib.goom_scan_real(None, None, None, p, 4, 8, 8, 1, 0, None, None, 0) == EINVAL
+    assert lib.goom_scan_real(None, p, None, p, 4096, 64, 64, 1, 0, C.byref(o), None, 0) == EWS
+    assert lib.goom_reduce_real(None, p, None, p, 4, 24, 24, 1, 0, None, None, 0) == EWS  # encoded copy needed
     # lmme
     assert lib.goom_lmme(None, p, p, p, 1, 2000, 8, 8, 0, 0, None, 0) == EUNSUP
     assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 1, 0, None, 0) == EUNSUP and "GOOM_C64" in err(lib)
@@ -107,6 +111,10 @@ def test_workspace_queries(lib):
     assert small == 2 * 64 * per  # 64 chunks: plain carry chain
     assert lib.goom_scan_workspace_bytes(1 << 20, 64, 64, 1, 1, C.byref(o)) > n
     assert lib.goom_scan_workspace_bytes(0, 64, 64, 1, 0, None) == 0
+    # real input: read directly at d = 64 (same workspace), through an encoded copy at d = 16
+    assert lib.goom_scan_real_workspace_bytes(1 << 20, 64, 64, 1, 0, C.byref(o)) == n
+    w16 = lib.goom_scan_workspace_bytes(4096, 16, 16, 2, 0, None)
+    assert lib.goom_scan_real_workspace_bytes(4096, 16, 16, 2, 0, None) >= w16 + 2 * 4096 * 16 * 16 * 8
     aff = lib.goom_affine_scan_workspace_bytes(65536, 32, 128, 0, None)
     assert aff > 0
     # scaled states come straight from the last phase at d = 32 (no room for GOOM states needed), at d = 8 they
