@@ -119,28 +119,26 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
         for (int q = 0; q < Q; ++q) {
             const int row = (tid + q * NT) / LPR;
             if (REAL) {
-                // binary exponents (frexp convention) take the place of the log2 magnitudes; all shifts are exact
-                float ex[4];
-                float u = -3.0e38f;
+                // binary exponents (frexp convention) take the place of the log2 magnitudes, in integer
+                // arithmetic throughout; all shifts are exact.  (A zero entry counts as exponent 0: the row
+                // shift only has to be large enough, and scaling by a power of two loses nothing.)
+                int rji[4], ei[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    ex[e] = C::exponent_of(it[q].a[e]) + rj[e];
-                    u = vmax_raw(u, it[q].a[e] != 0.0f ? ex[e] : -3.0e38f);
+                    rji[e] = (int)rj[e]; // row exponents are whole numbers
+                    ei[e] = __builtin_amdgcn_frexp_expf(it[q].a[e]) + rji[e];
                 }
-                int key = C::key_of(u);
+                int key = C::imax(C::imax(ei[0], ei[1]), C::imax(ei[2], ei[3]));
                 key = C::imax(key, C::dpp<0xB1>(key));
                 if (LPR >= 4) key = C::imax(key, C::dpp<0x4E>(key));
                 if (LPR >= 8) key = C::imax(key, C::dpp<0x141>(key));
                 if (LPR >= 16) key = C::imax(key, C::dpp<0x140>(key));
                 if (LPR >= 32) key = C::xor16_imax(key);
-                const float mx = C::of_key(key);
-                const bool zero_row = !(mx > -1.0e30f);
-                const float n = zero_row ? (BIAS ? 0.0f : -1.0e30f) : mx;
                 f4 y;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) y[e] = zero_row ? 0.0f : __builtin_ldexpf(it[q].a[e], (int)C::clamp_shift(rj[e] - n));
+                for (int e = 0; e < 4; ++e) y[e] = __builtin_ldexpf(it[q].a[e], rji[e] - key);
                 *reinterpret_cast<f4 *>(&tile[row * LDA + c4]) = y;
-                nsh[row] = n;
+                nsh[row] = (float)key;
                 continue;
             }
             const float re[4] = {it[q].a[0], it[q].a[2], it[q].b[0], it[q].b[2]};
