@@ -93,13 +93,14 @@ def lorenz96_jacobians(seed: int, T: int, d: int = 32, forcing: float = 8.0, dt:
     def f(v):
         return (np.roll(v, -1) - np.roll(v, 2)) * np.roll(v, 1) - v + forcing
 
-    for _ in range(burn_in):
-        x = x + dt * f(x)
     traj = np.empty((T + 1, d), dtype=np.float64)
-    traj[0] = x
-    for t in range(T):
-        x = x + dt * f(x)
-        traj[t + 1] = x
+    with np.errstate(over="ignore", invalid="ignore"):  # an escaping trajectory is reported below
+        for _ in range(burn_in):
+            x = x + dt * f(x)
+        traj[0] = x
+        for t in range(T):
+            x = x + dt * f(x)
+            traj[t + 1] = x
     if not np.all(np.isfinite(traj)) or np.abs(traj).max() > 1e3:
         raise FloatingPointError("Lorenz-96 trajectory left the attractor (Euler step too large)")
     xs = traj[:-1]
