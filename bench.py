@@ -17,6 +17,7 @@ import time
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix rate, published
+MFMA_F64_PEAK_TFLOPS = 78.6    # MI355X dense fp64 matrix rate, published
 
 
 def main():
@@ -386,6 +387,17 @@ def large_matrices(g, torch, dev, si):
                              "pct_of_mfma_peak": round(100 * 2.0 * n ** 3 * B / sec / 1e12 / MFMA_F32_PEAK_TFLOPS, 2),
                              "gemm_tflops": round(2.0 * n ** 3 * B / (kt["lmme_large_gemm"] * 1e-3) / 1e12, 2), "kernels_ms": kt}
     del a, b, c
+    # the same product with double components (complex128), on the double-precision matrix instruction
+    a = g.to_goom(torch.randn((B, n, n), device=dev, dtype=torch.float64, generator=si.device_generator(251003426 * 10 + 74, dev)))
+    b = g.to_goom(torch.randn((B, n, n), device=dev, dtype=torch.float64, generator=si.device_generator(251003426 * 10 + 75, dev)))
+    c = torch.empty_like(a)
+    sec = timed(torch, lambda: g.lmme(a, b, out=c), 5)
+    kt = kernel_times(g, lambda: g.lmme(a, b, out=c))
+    res["lmme_32x1024^3_complex128"] = {"ms": round(sec * 1e3, 3), "tflops": round(2.0 * n ** 3 * B / sec / 1e12, 2),
+                                        "pct_of_fp64_mfma_peak": round(100 * 2.0 * n ** 3 * B / sec / 1e12 / MFMA_F64_PEAK_TFLOPS, 2),
+                                        "gemm_tflops": round(2.0 * n ** 3 * B / (kt["lmme_large_gemm"] * 1e-3) / 1e12, 2), "kernels_ms": kt}
+    del a, b, c
+    torch.cuda.empty_cache()
     for T, d in ((512, 1024), (32768, 256)):
         z = torch.empty((T, d, d), dtype=torch.complex64, device=dev)
         for t0, x in si.device_normal_blocks(251003426 * 10 + 73, T, (d, d), dev, max(1, (1 << 26) // (d * d))):

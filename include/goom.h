@@ -67,8 +67,9 @@ typedef enum goom_dtype {
 
 /* largest matrix dimension of the register-resident kernels (scans, recurrences, small products) */
 #define GOOM_MAX_DIM 128
-/* largest dimension of goom_lmme (complex64): above GOOM_MAX_DIM the product runs as scaled operands,
- * a tiled GEMM and a store pass through the workspace (the paper's experiments go up to 1024) */
+/* largest dimension of goom_lmme (both formats) and of scans of complex64 matrices: above GOOM_MAX_DIM the
+ * product runs as scaled operands, a tiled GEMM and a store pass through the workspace (the paper's experiments
+ * go up to 1024) */
 #define GOOM_MAX_DIM_LMME 1024
 
 /* flags of goom_to_goom: how log 0 is written (paper Section 3.1, configurable real log) */
@@ -129,7 +130,8 @@ int goom_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype);
 /* ---- LMME (paper Section 3.2) ---------------------------------------------------- */
 
 /* C[b] = LMME(A[b], B[b]) = log(exp(A[b]) exp(B[b])) for b < batch.
- * A: [batch, n, d], B: [batch, d, m], C: [batch, n, m] GOOMs; 1 <= n, d, m <= GOOM_MAX_DIM.
+ * A: [batch, n, d], B: [batch, d, m], C: [batch, n, m] GOOMs; 1 <= n, d, m <= GOOM_MAX_DIM_LMME
+ * (above GOOM_MAX_DIM the workspace is required, and batch <= 65535).
  * Computed as the paper's scaled real product on the matrix cores (eq. 7) with row
  * shifts max_j Re A_ij and column shifts max_j Re B_jk (0 for an all-zero row/column).
  * A sum that is exactly zero gives (-inf, 0).  flags: GOOM_LMME_FAST or GOOM_LMME_EXACT.

@@ -608,9 +608,9 @@ static bool lmme_is_large(int n, int d, int m) { return n > GOOM_MAX_DIM || d > 
 size_t goom_lmme_workspace_bytes(int64_t batch, int n, int d, int m, int dtype, uint32_t flags)
 {
     (void)flags;
-    if (batch <= 0 || n <= 0 || d <= 0 || m <= 0 || dtype != GOOM_C64 || !lmme_is_large(n, d, m)) return 0;
+    if (batch <= 0 || n <= 0 || d <= 0 || m <= 0 || (dtype != GOOM_C64 && dtype != GOOM_C128) || !lmme_is_large(n, d, m)) return 0;
     if (n > GOOM_MAX_DIM_LMME || d > GOOM_MAX_DIM_LMME || m > GOOM_MAX_DIM_LMME) return 0;
-    return lmme_large_workspace_bytes(batch, n, d, m);
+    return dtype == GOOM_C64 ? lmme_large_workspace_bytes(batch, n, d, m) : lmme_large_f64_workspace_bytes(batch, n, d, m);
 }
 
 int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batch, int n, int d, int m, int dtype,
@@ -625,10 +625,12 @@ int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batc
     if (!aligned(A, 16) || !aligned(B, 16) || !aligned(C, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
     if (lmme_is_large(n, d, m)) {
         // beyond the register-resident kernels: scaled operands, a tiled GEMM and a store pass, through the workspace
-        if (dtype != GOOM_C64) return fail(ctx, GOOM_EUNSUPPORTED, "shapes above %d are built for GOOM_C64 only", GOOM_MAX_DIM);
-        if (int s = check_workspace(ctx, workspace, workspace_bytes, lmme_large_workspace_bytes(batch, n, d, m))) return s;
+        const bool f32 = dtype == GOOM_C64;
+        const size_t need = f32 ? lmme_large_workspace_bytes(batch, n, d, m) : lmme_large_f64_workspace_bytes(batch, n, d, m);
+        if (int s = check_workspace(ctx, workspace, workspace_bytes, need)) return s;
         if (int s = need_ctx(ctx)) return s;
-        if (int s = launch_lmme_large(ctx, A, B, C, batch, n, d, m, workspace)) return s;
+        if (int s = f32 ? launch_lmme_large(ctx, A, B, C, batch, n, d, m, workspace) : launch_lmme_large_f64(ctx, A, B, C, batch, n, d, m, workspace))
+            return s;
         if (flags & GOOM_LMME_EXACT) return launch_lmme_exact(ctx, A, B, C, batch, n, d, m, dtype);
         return GOOM_OK;
     }

@@ -118,6 +118,9 @@ int launch_uniform_u0(goom_ctx *ctx, void *u, long long batch, int d, int dtype)
 
 size_t lmme_large_workspace_bytes(long long batch, int n, int d, int m);
 int launch_lmme_large(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int n, int d, int m, void *ws);
+// the same for complex128 operands (double components, double-precision matrix instruction)
+size_t lmme_large_f64_workspace_bytes(long long batch, int n, int d, int m);
+int launch_lmme_large_f64(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int n, int d, int m, void *ws);
 // chains of matrices with 128 < d <= 256: register-resident state, one workgroup per 128 state columns
 int launch_row_shifts256(goom_ctx *ctx, const void *M, float *nrow, int d, long long nmat);
 int launch_chain256(goom_ctx *ctx, const void *M, const float *nrow, long long T, long long L, long long chunks, long long batch, int d, int m,

@@ -691,6 +691,26 @@ def test_affine_scan_time_invariant(G, oracle, T, d, batch, chunk, ctype):
 
 # ------------------------------------------- shapes beyond the register-resident kernels (up to 1024)
 
+@pytest.mark.parametrize("shape", [(2, 256, 256, 256), (1, 300, 200, 150), (3, 129, 64, 64), (1, 40, 500, 33), (1, 512, 512, 512)])
+def test_lmme_large_shapes_complex128(G, oracle, shape):
+    """The same passes with double components on the double-precision matrix instruction."""
+    from paper_2510_03426_amd import LMME_EXACT
+    b, n, d, m = shape
+    A = oracle.to_goom(si.normal_f32(si.BASE_SEED + 64, 5, b * n * d).reshape(b, n, d).astype(np.float64))
+    B = oracle.to_goom(si.normal_f32(si.BASE_SEED + 65, 6, b * d * m).reshape(b, d, m).astype(np.float64))
+    assert A.dtype == np.complex128
+    say(f"large lmme complex128 {shape}")
+    re, sg, kap = oracle.lmme(A, B, return_kappa=True)
+    got = host(G.lmme(dev(A), dev(B)))
+    compare(got, re, sg, kap, name=f"large lmme c128 {shape}", max_ill_fraction=0.01)
+    if n * d * m <= 256 ** 3:
+        # log-magnitudes N(0, 200^2): the scaled product with its repair pass
+        A2, B2 = si.wide_range_goom_pairs(si.BASE_SEED + 66, b, n, d, m, sigma=200.0, dtype=np.complex128)
+        re, sg, kap = oracle.lmme(A2, B2, return_kappa=True)
+        got = host(G.lmme(dev(A2), dev(B2), flags=LMME_EXACT))
+        compare(got, re, sg, kap, name=f"large lmme c128 wide, repaired {shape}", max_ill_fraction=0.01)
+
+
 @pytest.mark.parametrize("shape", [(2, 256, 256, 256), (1, 300, 200, 150), (3, 129, 64, 64), (1, 40, 500, 33), (1, 512, 512, 512),
                                    (1, 1024, 1024, 1024)])
 def test_lmme_large_shapes(G, oracle, shape):
