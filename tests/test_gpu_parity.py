@@ -691,7 +691,8 @@ def test_affine_scan_time_invariant(G, oracle, T, d, batch, chunk, ctype):
 
 # ------------------------------------------- shapes beyond the register-resident kernels (up to 1024)
 
-@pytest.mark.parametrize("shape", [(2, 256, 256, 256), (1, 300, 200, 150), (3, 129, 64, 64), (1, 40, 500, 33), (1, 512, 512, 512)])
+@pytest.mark.parametrize("shape", [(2, 256, 256, 256), (1, 300, 200, 150), (3, 129, 64, 64), (1, 40, 500, 33), (1, 512, 512, 512),
+                                   (1, 1024, 1024, 1024), (2, 1000, 130, 1024)])
 def test_lmme_large_shapes_complex128(G, oracle, shape):
     """The same passes with double components on the double-precision matrix instruction."""
     from paper_2510_03426_amd import LMME_EXACT
