@@ -45,10 +45,15 @@ template <int CTRL> __device__ inline float add_dpp(float x)
 
 // REAL: the left factors are plain real matrices (4 bytes per entry instead of a GOOM's 8): an entry is
 // scaled by 2^(r_j - n_i) exactly, with no logarithm or exponential on the way in.
-template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void chain_body(const ChainArgs &a)
+// RAG: square matrices of a size d < DP that is a multiple of four (rows d entries apart in memory): the
+// tile's rows and columns from d on are zero, only the first KD = ceil(d / 16) blocks of sixteen rows and
+// columns take part in the product, and waves whose sixteen state columns lie beyond d only help converting.
+template <int DP, int NW, bool BIAS, bool REAL, int KD = DP / 16, bool RAG = false>
+__device__ __forceinline__ void chain_body(const ChainArgs &a)
 {
     typedef Comp<float> C;
-    constexpr int KT = DP / 16;
+    static_assert(!RAG || (!BIAS && !REAL && KD <= DP / 16), "ragged sizes: GOOM factors, no bias column");
+    constexpr int KT = KD;
     constexpr int LDA = DP + 4;
     constexpr int NWT = NW + (BIAS ? 1 : 0); // waves, one per 16-column slab of the state
     constexpr int M = 16 * NWT;  // state columns
@@ -76,6 +81,8 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
     const int c4 = 4 * (tid % LPR); // first of this lane's four factor columns
     const bool converter = !BIAS || wave < NW;
     const bool bias_wave = BIAS && wave == NW;
+    const bool owner = !RAG || wave < KD; // this wave owns sixteen columns of the state
+    const int dd = RAG ? a.d : DP;        // size of the matrices in memory
     // bias wave: lane -> row and part of the contraction index
     constexpr int LPRB = DP >= 64 ? 1 : 64 / DP; // lanes per row
     constexpr int CPLB = DP / LPRB;              // contraction indices per lane
@@ -98,6 +105,13 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
             const int row = (tid + q * NT) / LPR;
             if (REAL) {
                 it[q].a = *reinterpret_cast<const f4 *>(src + (size_t)row * DP + c4);
+            } else if (RAG) {
+                // entries beyond the matrix are read from its last row / last four columns instead (and
+                // discarded by the conversion), so that no load sits behind a branch
+                const int rr = row < dd ? row : dd - 1, cc = c4 < dd ? c4 : dd - 4;
+                const f4 *gp = reinterpret_cast<const f4 *>(src + ((size_t)rr * dd + cc) * 2);
+                it[q].a = gp[0];
+                it[q].b = gp[1];
             } else {
                 const f4 *gp = reinterpret_cast<const f4 *>(src + ((size_t)row * DP + c4) * 2);
                 it[q].a = gp[0];
@@ -114,6 +128,9 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
         float *tile = tile_of(buf);
         float *nsh = nsh_of(buf);
         f4 rj = {0.f, 0.f, 0.f, 0.f};
+        // (ragged: columns beyond the matrix carry the exponent of a zero row, which the rows beyond the
+        // matrix hand on from step to step; it makes their entries vanish)
+        if (RAG && c4 >= dd) rj = f4{-1.0e30f, -1.0e30f, -1.0e30f, -1.0e30f};
         if (rsrc) rj = *reinterpret_cast<const f4 *>(&rsrc[c4]);
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
@@ -156,7 +173,7 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
             float mx = C::of_key(key);
             // a row that is entirely zero keeps a finite (hugely negative) shift, and its
             // exponent arguments are forced to -inf so that nothing can overflow
-            const bool zero_row = !(mx > -1.0e30f);
+            const bool zero_row = !(mx > -1.0e30f) || (RAG && row >= dd);
             // (with a bias column the shift of such a row must stay small: the bias is scaled by it)
             const float n = zero_row ? (BIAS ? 0.0f : -1.0e30f) : __builtin_ceilf(mx);
             const float nsub = zero_row ? __builtin_huge_valf() : n;
@@ -184,7 +201,12 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) st[kt][v] = (a.init_mode == 0 && 16 * kt + 4 * g + v == col) ? 1.0f : 0.0f;
+            for (int v = 0; v < 4; ++v) st[kt][v] = (a.init_mode == 0 && 16 * kt + 4 * g + v == col && col < dd) ? 1.0f : 0.0f;
+    } else if (!owner) {
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) st[kt][v] = 0.0f;
     } else if (a.init_mode == 1) {
         long long iidx = chain_global;
         if (a.init_group > 0) {
@@ -202,11 +224,20 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
         ecol = ep[col];
     } else {
         const float *gp = reinterpret_cast<const float *>(a.init + item * a.init_stride);
+        const int MM = RAG ? dd : M; // columns of the initial state in memory
+        // (ragged: entries beyond the matrix are read from its last row / column and replaced by zeros)
+        const int colc = RAG ? (col < dd ? col : dd - 1) : col;
+        auto init_row = [&](int r) { return RAG ? (r < dd ? r : dd - 1) : r; };
+        auto init_ok = [&](int r) { return !RAG || (r < dd && col < dd); };
         float cmax = C::neg_inf();
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) cmax = C::max_(cmax, gp[((size_t)(16 * kt + 4 * g + v) * M + col) * 2]);
+            for (int v = 0; v < 4; ++v) {
+                const int r = 16 * kt + 4 * g + v;
+                const float re = gp[((size_t)init_row(r) * MM + colc) * 2];
+                cmax = C::max_(cmax, init_ok(r) ? re : C::neg_inf());
+            }
         cmax = C::xor16_32_max(cmax);
         // the column's exponent: a whole number near its largest log2 magnitude that a float holds exactly
         const float ecol_f = (cmax > C::neg_inf()) ? (float)__builtin_ceil((double)cmax * kLog2e) : 0.0f;
@@ -215,8 +246,9 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float2 e = *reinterpret_cast<const float2 *>(gp + ((size_t)(16 * kt + 4 * g + v) * M + col) * 2);
-                st[kt][v] = C::apply_sign(C::exp2_shifted(e.x, ecol_f), e.y);
+                const int r = 16 * kt + 4 * g + v;
+                const float2 e = *reinterpret_cast<const float2 *>(gp + ((size_t)init_row(r) * MM + colc) * 2);
+                st[kt][v] = init_ok(r) ? C::apply_sign(C::exp2_shifted(e.x, ecol_f), e.y) : 0.0f;
             }
     }
 
@@ -256,7 +288,7 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
             }
             if (LPRB >= 2) accb = add_dpp<0xB1>(accb);
             if (LPRB >= 4) accb = add_dpp<0x4E>(accb);
-        } else {
+        } else if (owner) {
 #pragma unroll
             for (int mt = 0; mt < KT; ++mt) acc[mt] = f4{0, 0, 0, 0};
 #pragma unroll
@@ -300,8 +332,8 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
 
         // ------------------------------------------------------------ outputs
         // entry (i = 16 mt + 4 g + v, col) of the product is acc 2^(n_i + ecol)
-        const bool want_out = a.out_goom && (!a.out_goom_last_only || last) && !bias_wave;
-        if (want_out) {
+        const bool want_out = a.out_goom && (!a.out_goom_last_only || last) && !bias_wave && owner;
+        if (want_out && !RAG) {
             const long long o_idx = a.out_goom_last_only ? chain_global : (item * a.steps + t0 + t);
             float *outp = reinterpret_cast<float *>(a.out_goom) + ((size_t)o_idx * DP * M + (size_t)(4 * g) * M + col) * 2;
             const float ecol_f = (float)ecol;
@@ -314,6 +346,26 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
                     const float re = C::out_re_f(x, nv[v] + ecol_f);
                     const float im = x < 0.0f ? C::pi() : 0.0f;
                     *reinterpret_cast<float2 *>(outp + (size_t)(16 * mt + v) * M * 2) = float2{re, im};
+                }
+            }
+        }
+        if (want_out && RAG) {
+            // rows d entries apart; a lane's four rows 16 mt + 4 g + v lie inside the matrix together (d is a
+            // multiple of four)
+            const long long o_idx = a.out_goom_last_only ? chain_global : (item * a.steps + t0 + t);
+            float *outp = reinterpret_cast<float *>(a.out_goom) + ((size_t)o_idx * dd * dd + (size_t)(4 * g) * dd + col) * 2;
+            const float ecol_f = (float)ecol;
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                if (16 * mt + 4 * g < dd && col < dd) {
+                    const f4 nv = *reinterpret_cast<const f4 *>(&nsh[16 * mt + 4 * g]);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float x = acc[mt][v];
+                        const float re = C::out_re_f(x, nv[v] + ecol_f);
+                        const float im = x < 0.0f ? C::pi() : 0.0f;
+                        *reinterpret_cast<float2 *>(outp + (size_t)(16 * mt + v) * dd * 2) = float2{re, im};
+                    }
                 }
             }
         }
@@ -336,6 +388,8 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
                 ecol += (double)cm;
             }
             if (lane % LPRB == 0) wvec[brow] = accb;
+        } else if (!owner) {
+            // (no state columns)
         } else if (!last) {
             // keep the raw product; its row exponents n_i go to the next factor's columns
 #pragma unroll
@@ -391,7 +445,7 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
         cm = C::xor16_32_max(cm);
         // (the bias column is not contracted over when the product serves as a left factor: it
         // keeps an exponent of its own, so a bias far above or below A* costs neither any bits)
-        double ev = (cm > 0.0f && !bias_wave) ? ecol : kNegBig;
+        double ev = (cm > 0.0f && !bias_wave && owner) ? ecol : kNegBig;
 #pragma unroll
         for (int s = 1; s < 16; s <<= 1) {
             const double o = shfl_xor_double(ev, s);
@@ -409,14 +463,14 @@ template <int DP, int NW, bool BIAS, bool REAL> __device__ __forceinline__ void 
             // column d from the lanes that own its rows; the padding columns behind it are zero
             if (lane % LPRB == 0) mp[(size_t)brow * a.fact_cols + DP] = wvec[brow];
             for (int idx = lane; idx < DP * 15; idx += 64) mp[(size_t)(idx / 15) * a.fact_cols + DP + 1 + idx % 15] = 0.0f;
-        } else {
+        } else if (owner) {
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
                     mp[(size_t)(16 * kt + 4 * g + v) * a.fact_cols + col] = __builtin_ldexpf(st[kt][v], shift);
         }
-        if (g == 0) ep[col] = bias_wave ? ecol : emax;
+        if (g == 0 && owner) ep[col] = bias_wave ? ecol : emax;
     }
 }
 
@@ -431,6 +485,13 @@ template <int DP, int NW>
 __global__ __launch_bounds__(NW * 64, (DP <= 16 ? 8 : DP == 32 ? 6 : DP == 64 ? 4 : 2)) void chain_kernel_fast_real(ChainArgs a)
 {
     chain_body<DP, NW, false, true>(a);
+}
+
+// square matrices of a size below DP (a multiple of four), KD = ceil(d / 16) blocks of sixteen
+template <int DP, int NW, int KD>
+__global__ __launch_bounds__(NW * 64, (DP == 32 ? 6 : DP == 64 ? 4 : 2)) void chain_kernel_fast_ragged(ChainArgs a)
+{
+    chain_body<DP, NW, false, false, KD, true>(a);
 }
 
 template <int DP, int NW, bool BIAS, bool REAL = false> int launch_fast(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
@@ -470,6 +531,11 @@ bool affine_walk_applies(const ChainArgs &args, int dp);
 int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label);
 int launch_replicate_power(goom_ctx *ctx, void *totals, long long stride, int fact_cols, int dp, int d, long long batch,
                            long long chunks, long long chunks_per_item);
+
+// square matrices whose size is a multiple of four between the sizes above (20 ... 124): the hot kernel
+// with the rows and columns beyond the matrix left out, separate translation unit
+bool ragged_applies(const ChainArgs &args, int dp, int nw);
+int dispatch_ragged(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label);
 
 // 8 x 8 and 16 x 16 chains: one wave per chain (or per pair of 8 x 8 chains), separate translation unit
 bool small_applies(const ChainArgs &args);

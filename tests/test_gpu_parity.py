@@ -262,6 +262,31 @@ def test_scan_sizes_and_ragged_tails(G, oracle, T, d, chunk):
     run_scan_case(G, oracle, T, d, chunk, name=f"T{T}d{d}")
 
 
+@pytest.mark.parametrize("T,d,chunk,m,batch", [(90, 20, 16, None, 1), (300, 24, 0, None, 2), (61, 28, 7, 28, 1), (120, 36, 16, None, 1),
+                                                (200, 48, 0, 48, 2), (77, 52, 10, None, 1), (64, 60, 16, None, 1), (40, 68, 8, None, 1),
+                                                (70, 96, 16, 96, 1), (33, 100, 8, None, 2), (24, 124, 5, None, 1), (1, 48, 0, None, 1)])
+def test_scan_sizes_between_the_tiles(G, oracle, T, d, chunk, m, batch):
+    # square matrices whose size is a multiple of four but not a tile size: the hot kernel with rows and columns
+    # beyond the matrix left out (all block counts, with and without an initial state, single steps, batches)
+    x = si.normal_f32(si.BASE_SEED + 95, 1, batch * T * d * d).reshape(batch, T, d, d)
+    if T > 4:
+        x[0, 2, d - 1, :] = 0.0   # a zero last row
+        x[0, 3, :, d - 1] = 0.0   # a zero last column
+        x[0, 4, 0, :] = 0.0
+    Z = oracle.to_goom(x)
+    init = None
+    if m is not None:
+        init = oracle.to_goom(si.normal_f32(si.BASE_SEED + 96, 2, batch * d * m).reshape(batch, d, m))
+    say(f"scan between tiles: T={T} d={d} m={m} batch={batch} chunk_len={chunk}")
+    out = host(G.scan(dev(Z), None if init is None else dev(init), chunk_len=chunk))
+    red = host(G.reduce(dev(Z), None if init is None else dev(init), chunk_len=chunk))
+    for b in range(batch):
+        fn = lambda mats, ini: oracle.scan(mats, init=ini, return_kappa=True)
+        re, sg, kap, well = with_sensitivity(fn, [Z[b], None if init is None else init[b]], np.float32)
+        compare(out[b], re, sg, kap, name=f"d{d} scan b{b}", max_ill_fraction=0.03, well=well)
+        compare(red[b], re[-1], sg[-1], kap[-1], name=f"d{d} reduce b{b}", max_ill_fraction=0.06, well=well[-1])
+
+
 def test_scan_small_matrices_in_pairs(G, oracle):
     # 8 x 8 chains share a wave two by two: pairs that straddle batch items, a ragged last chunk that is shorter
     # than its partner, an odd number of chains, single steps; 16 x 16 chains one per wave
