@@ -33,7 +33,7 @@ def main():
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs")
     ap.add_argument("--no-extras", action="store_true", help="time the headline scan only")
-    ap.add_argument("--only", choices=["tiny", "scan128", "lmme", "lyapunov", "recurrence", "large"], default=None,
+    ap.add_argument("--only", choices=["tiny", "between", "scan128", "lmme", "lyapunov", "recurrence", "large"], default=None,
                     help="time just one of the other workloads (for profiler runs) and print its figures")
     ap.add_argument("--basic-extras", action="store_true",
                     help="besides the scan, time only a plain device copy of the same size (for counter runs)")
@@ -256,6 +256,8 @@ def other_workloads(g, torch, dev, only=None):
     if want("tiny"):
         res["scan_T256_d8"] = tiny_scan(g, torch, dev, si)
         res.update(small_scans(g, torch, dev, si))
+    if want("between"):
+        res.update(scans_between_tiles(g, torch, dev, si))
     if want("scan128"):
         res.update(scan128(g, torch, dev, si))
     if want("lmme"):
@@ -287,6 +289,23 @@ def small_scans(g, torch, dev, si):
         res[f"scan_T{T}_d{d}"] = {"ms": round(sec * 1e3, 3), "products_per_s": round(T / sec, 1),
                                   "hbm_gbs_algorithmic": round(byts / sec / 1e9, 1),
                                   "pct_of_hbm_peak": round(100 * byts / sec / 1e9 / HBM_PEAK_GBS, 2),
+                                  "kernels_ms": kernel_times(g, lambda: g.scan(z, out=out))}
+        del z, out
+    return res
+
+
+def scans_between_tiles(g, torch, dev, si):
+    # sizes that are not a tile size (the hot kernel with the padding left out of the product): 48 x 48 and 96 x 96
+    res = {}
+    for d, T in ((48, 1 << 19), (96, 1 << 17)):
+        z = g.to_goom(torch.randn((T, d, d), device=dev, generator=si.device_generator(251003426 * 10 + 90 + d, dev)))
+        out = torch.empty_like(z)
+        sec = timed(torch, lambda: g.scan(z, out=out), 5)
+        byts = 3 * z.numel() * 8  # read, read, write
+        fl = 2.0 * d ** 3 * 2 * T
+        res[f"scan_T{T}_d{d}"] = {"ms": round(sec * 1e3, 3), "products_per_s": round(T / sec, 1),
+                                  "hbm_gbs_algorithmic": round(byts / sec / 1e9, 1),
+                                  "lmme_tflops_executed": round(fl / sec / 1e12, 2),
                                   "kernels_ms": kernel_times(g, lambda: g.scan(z, out=out))}
         del z, out
     return res
