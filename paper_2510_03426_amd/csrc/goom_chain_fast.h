@@ -63,6 +63,11 @@ __device__ __forceinline__ void chain_body(const ChainArgs &a)
     constexpr int Q = NITEMS / NT; // items per thread
     constexpr int kRenormEvery = 4;
     static_assert(NITEMS % NT == 0 && NT % LPR == 0, "tile does not divide among the threads");
+    // A pass of all converting threads covers NT / LPR rows of the factor.  Ragged sizes: that is sixteen rows,
+    // so only the first KD passes hold rows that take part in the product; the others are neither loaded nor
+    // converted (their row exponents, those of zero rows, are written once at the start).
+    static_assert(!RAG || (NT / LPR == 16 && Q == DP / 16), "ragged sizes: one pass per block of sixteen rows");
+    constexpr int QE = RAG ? KD : Q;
     constexpr size_t kTileBytes = (size_t)DP * LDA * sizeof(float);
     constexpr size_t kBufBytes = kTileBytes + (size_t)DP * sizeof(float);
 
@@ -101,7 +106,7 @@ __device__ __forceinline__ void chain_body(const ChainArgs &a)
     auto load_items = [&](long long t, Item4 (&it)[Q]) {
         const float *src = reinterpret_cast<const float *>(left0 + t * a.left_step_stride);
 #pragma unroll
-        for (int q = 0; q < Q; ++q) {
+        for (int q = 0; q < QE; ++q) {
             const int row = (tid + q * NT) / LPR;
             if (REAL) {
                 it[q].a = *reinterpret_cast<const f4 *>(src + (size_t)row * DP + c4);
@@ -133,7 +138,7 @@ __device__ __forceinline__ void chain_body(const ChainArgs &a)
         if (RAG && c4 >= dd) rj = f4{-1.0e30f, -1.0e30f, -1.0e30f, -1.0e30f};
         if (rsrc) rj = *reinterpret_cast<const f4 *>(&rsrc[c4]);
 #pragma unroll
-        for (int q = 0; q < Q; ++q) {
+        for (int q = 0; q < QE; ++q) {
             const int row = (tid + q * NT) / LPR;
             if (REAL) {
                 // binary exponents (frexp convention) take the place of the log2 magnitudes, in integer
@@ -253,6 +258,9 @@ __device__ __forceinline__ void chain_body(const ChainArgs &a)
     }
 
     Item4 pre[Q];
+    if (RAG) {
+        for (int i = 16 * KD + tid; i < DP; i += NT) nsh_of(0)[i] = nsh_of(1)[i] = -1.0e30f;
+    }
     if (len > 0 && converter) {
         load_items(0, pre);
         convert_items(pre, 0, nullptr);
