@@ -73,7 +73,8 @@ def test_argument_validation_without_device(lib):
     assert lib.goom_reduce_real(None, p, None, p, 4, 24, 24, 1, 0, None, None, 0) == EWS  # encoded copy needed
     # lmme
     assert lib.goom_lmme(None, p, p, p, 1, 2000, 8, 8, 0, 0, None, 0) == EUNSUP
-    assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 1, 0, None, 0) == EUNSUP and "GOOM_C64" in err(lib)
+    assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 1, 0, None, 0) == EWS  # complex128 above 128: through the workspace too
+    assert lib.goom_scan(None, p, None, p, 4, 200, 200, 1, 1, None, None, 0) == EUNSUP and "GOOM_C64" in err(lib)
     assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 0, 0, None, 0) == EWS
     assert lib.goom_lmme_workspace_bytes(1, 200, 8, 8, 0, 0) > 0
     assert lib.goom_lmme(None, p, p, p, 0, 8, 8, 8, 0, 0, None, 0) == EINVAL
@@ -122,6 +123,10 @@ def test_workspace_queries(lib):
     assert lib.goom_affine_scan_scaled_workspace_bytes(65536, 32, 128, 0, None) < aff + 256
     assert lib.goom_affine_scan_scaled_workspace_bytes(65536, 8, 128, 0, None) >= 128 * 65536 * 8 * 8
     assert lib.goom_lmme_workspace_bytes(8192, 128, 128, 128, 0, 0) == 0
+    # above 128: scaled operands, their shifts and the transposed product, in the component type
+    w32 = lib.goom_lmme_workspace_bytes(2, 1024, 1024, 1024, 0, 0)
+    w64 = lib.goom_lmme_workspace_bytes(2, 1024, 1024, 1024, 1, 0)
+    assert w32 == 2 * (3 * 1024 * 1024 + 2 * 1024) * 4 and w64 == 2 * w32
 
 
 def test_product_path_has_no_cpu_fallback():
