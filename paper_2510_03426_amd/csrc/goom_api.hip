@@ -126,7 +126,9 @@ static ScanPlan plan_scan(long long T, int d, int m_tot, int m_state, long long 
                           long long requested_chunk, bool final_only)
 {
     ScanPlan p;
-    p.dp = padded_dim(d);
+    // one tile size for every phase (the factored matrices they hand to each other have that many rows): wide
+    // enough for the widest state
+    p.dp = chain_padded_dim(d, d, m_tot > m_state ? m_tot : m_state);
     p.L = default_chunk_len(T, batch, requested_chunk, p.dp);
     p.C = (T + p.L - 1) / p.L;
     p.nt = final_only ? p.C : p.C - 1;
@@ -192,6 +194,7 @@ static int carry_phase(goom_ctx *ctx, const ScanPlan &p, int dtype, int d, long 
 {
     ChainLaunch base;
     std::memset(&base, 0, sizeof base);
+    base.dp = p.dp;
     base.dtype = dtype;
     base.n = d;
     base.d = d;
@@ -305,6 +308,7 @@ static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, lon
 
     ChainLaunch base;
     std::memset(&base, 0, sizeof base);
+    base.dp = p.dp;
     base.dtype = dtype;
     base.n = d;
     base.d = d;

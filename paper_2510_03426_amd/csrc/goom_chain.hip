@@ -29,9 +29,16 @@ static int pick_waves(int dp, int nslabs)
     return -1;
 }
 
+int chain_padded_dim(int n, int d, int m)
+{
+    int dp = padded_dim(n > d ? n : d);
+    while (dp < 128 && pick_waves(dp, (m + 15) / 16) < 0) dp *= 2;
+    return dp;
+}
+
 int launch_chain(goom_ctx *ctx, const ChainLaunch &l)
 {
-    const int dp = padded_dim(l.n > l.d ? l.n : l.d);
+    const int dp = l.dp ? l.dp : chain_padded_dim(l.n, l.d, l.m);
     const int nslabs = (l.m + 15) / 16;
     const int nw = pick_waves(dp, nslabs);
     if (nw < 0) return fail(ctx, GOOM_EUNSUPPORTED, "state of %d columns with d = %d is not supported", l.m, l.d);

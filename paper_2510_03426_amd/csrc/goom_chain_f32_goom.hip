@@ -4,7 +4,7 @@
 namespace goom_chain {
 int dispatch_f32_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label)
 {
-    if (small_applies(args)) return dispatch_small(ctx, args, grid, label);
+    if (small_applies(args, dp)) return dispatch_small(ctx, args, grid, label);
     if (fast_applies(args, dp, nw)) return dispatch_fast(ctx, args, dp, grid, label);
     if (ragged_applies(args, dp, nw)) return dispatch_ragged(ctx, args, dp, grid, label);
     if (args.left_real) return goom::fail(ctx, GOOM_EUNSUPPORTED, "real left factors are read by the hot float kernel only (d = 32, 64 or 128, square state)");

@@ -86,8 +86,10 @@ __device__ __forceinline__ void chain_body(const ChainArgs &a)
     const int c4 = 4 * (tid % LPR); // first of this lane's four factor columns
     const bool converter = !BIAS || wave < NW;
     const bool bias_wave = BIAS && wave == NW;
-    const bool owner = !RAG || wave < KD; // this wave owns sixteen columns of the state
     const int dd = RAG ? a.d : DP;        // size of the matrices in memory
+    // this wave owns sixteen columns of the state (KD may exceed ceil(d / 16) when a wider state elsewhere in
+    // the same scan has fixed the tile size; the factored product stored at the end has ceil(d / 16) slabs)
+    const bool owner = !RAG || (wave < KD && 16 * wave < dd);
     // bias wave: lane -> row and part of the contraction index
     constexpr int LPRB = DP >= 64 ? 1 : 64 / DP; // lanes per row
     constexpr int CPLB = DP / LPRB;              // contraction indices per lane
@@ -546,7 +548,7 @@ bool ragged_applies(const ChainArgs &args, int dp, int nw);
 int dispatch_ragged(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label);
 
 // 8 x 8 and 16 x 16 chains: one wave per chain (or per pair of 8 x 8 chains), separate translation unit
-bool small_applies(const ChainArgs &args);
+bool small_applies(const ChainArgs &args, int dp);
 int dispatch_small(goom_ctx *ctx, const ChainArgs &args, long long nchains, const char *label);
 
 inline int dispatch_fast(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label)

@@ -251,9 +251,10 @@ template <int D, bool OUT> int launch_small(goom_ctx *ctx, const ChainArgs &args
 
 } // namespace
 
-bool small_applies(const ChainArgs &args)
+bool small_applies(const ChainArgs &args, int dp)
 {
-    return (args.d == 8 || args.d == 16) && args.n == args.d && args.m == args.d && args.bias_mode == 0 && args.out_fact_steps == nullptr &&
+    // (dp above 16: a wider state elsewhere in the same scan fixes the layout of the factored matrices)
+    return dp == 16 && (args.d == 8 || args.d == 16) && args.n == args.d && args.m == args.d && args.bias_mode == 0 && args.out_fact_steps == nullptr &&
            (args.init_mode == 0 || args.init_mode == 1) && !args.out_goom_last_only && args.out_scaled == nullptr && !args.left_real &&
            (args.out_goom != nullptr || args.out_fact_final != nullptr) && (args.out_fact_final == nullptr || args.fact_cols >= 16);
 }

@@ -51,9 +51,13 @@ struct FactLayout {
 };
 FactLayout fact_layout(int dp, int m, int dtype);
 int padded_dim(int d);
+// padded tile size for left factors n x d and a state of m columns: the smallest size that holds the factor
+// and whose workgroup has a wave for every sixteen columns of the state
+int chain_padded_dim(int n, int d, int m);
 
 // ---- kernel launchers (defined in the .hip files) ---------------------------------
 struct ChainLaunch {
+    int dp;               // padded size of the tile (rows of every factored matrix); 0: chain_padded_dim(n, d, m)
     int dtype;            // GOOM_C64 / GOOM_C128
     int n;                // rows of the left factors and of the outputs (= d for chains)
     int d;                // columns of the left factors, rows of the state

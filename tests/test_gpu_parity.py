@@ -169,7 +169,8 @@ def test_decode_accepts_any_phase_multiple(G, oracle):
 # -------------------------------------------------------------------------------- LMME
 
 @pytest.mark.parametrize("shape", [(1, 8, 8, 8), (3, 16, 16, 16), (2, 5, 7, 3), (2, 64, 64, 64), (2, 128, 128, 128),
-                                   (1, 33, 20, 1), (2, 1, 1, 1), (1, 100, 128, 60)])
+                                   (1, 33, 20, 1), (2, 1, 1, 1), (1, 100, 128, 60), (2, 3, 32, 64), (1, 31, 1, 128), (2, 1, 17, 128),
+                                   (1, 16, 4, 40)])
 def test_lmme_matches_oracle(G, oracle, shape):
     b, n, d, m = shape
     say(f"lmme batch={b} n={n} d={d} m={m}")
@@ -344,6 +345,15 @@ def test_scan_with_initial_state_and_batch(G, oracle):
     run_scan_case(G, oracle, 120, 32, 16, m=32, batch=3, seed=1, name="init square batch3")
     run_scan_case(G, oracle, 120, 64, 25, m=1, batch=2, seed=2, name="init vector")
     run_scan_case(G, oracle, 90, 16, 8, m=24, batch=1, seed=3, name="init wide")
+
+
+def test_scan_with_wide_initial_state(G, oracle):
+    # a state with many more columns than the matrices have rows: every phase runs on the tile size that
+    # gives each sixteen state columns a wave
+    run_scan_case(G, oracle, 70, 16, 8, m=64, batch=2, seed=41, name="d16 m64")
+    run_scan_case(G, oracle, 40, 32, 0, m=128, seed=42, name="d32 m128")
+    run_scan_case(G, oracle, 33, 8, 5, m=100, seed=43, name="d8 m100")
+    run_scan_case(G, oracle, 25, 24, 4, m=60, seed=44, dtype=np.float64, name="d24 m60 double")
 
 
 def test_scan_double_components(G, oracle):
