@@ -430,6 +430,18 @@ def large_matrices(g, torch, dev, si):
                                   "kernels_ms": kernel_times(g, lambda: g.scan(z, out=out))}
         del z, out
         torch.cuda.empty_cache()
+    # a scan of complex128 matrices above 128: T = 256 of 512 x 512 (the same driver on the fp64 GEMM)
+    T, d = 256, 512
+    z = g.to_goom(torch.randn((T, d, d), device=dev, dtype=torch.float64, generator=si.device_generator(251003426 * 10 + 76, dev)))
+    out = torch.empty_like(z)
+    sec = timed(torch, lambda: g.scan(z, out=out), 3)
+    fl = 2.0 * d ** 3 * 2 * T
+    res[f"scan_T{T}_d{d}_complex128"] = {"ms": round(sec * 1e3, 3), "products_per_s": round(T / sec, 1),
+                                         "lmme_tflops_executed": round(fl / sec / 1e12, 2),
+                                         "pct_of_fp64_mfma_peak": round(100 * fl / sec / 1e12 / MFMA_F64_PEAK_TFLOPS, 2),
+                                         "kernels_ms": kernel_times(g, lambda: g.scan(z, out=out))}
+    del z, out
+    torch.cuda.empty_cache()
     return res
 
 

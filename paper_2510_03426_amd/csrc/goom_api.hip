@@ -159,8 +159,6 @@ static int check_scan_args(goom_ctx *ctx, const void *M, const void *out, long l
     if (!M || !out) return fail(ctx, GOOM_EINVAL, "null data pointer");
     if (T <= 0 || batch <= 0 || d <= 0 || m <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive (T=%lld d=%d m=%d batch=%lld)", T, d, m, batch);
     if (d > max_dim || m > max_dim) return fail(ctx, GOOM_EUNSUPPORTED, "d and m must be <= %d (d=%d m=%d)", max_dim, d, m);
-    if ((d > GOOM_MAX_DIM || m > GOOM_MAX_DIM) && dtype != GOOM_C64)
-        return fail(ctx, GOOM_EUNSUPPORTED, "matrices above %d are built for GOOM_C64 only", GOOM_MAX_DIM);
     if (opts && opts->flags != 0) return fail(ctx, GOOM_EINVAL, "unknown scan flags 0x%x", opts->flags);
     if (opts && opts->chunk_len < 0) return fail(ctx, GOOM_EINVAL, "negative chunk_len");
     if (!aligned(M, 16) || !aligned(out, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
@@ -297,9 +295,12 @@ static int run_scan(goom_ctx *ctx, const void *M, const void *init, void *P, lon
     if (d > GOOM_MAX_DIM || m > GOOM_MAX_DIM) {
         // the state no longer fits a workgroup: chains advance step by step through a tiled GEMM
         const long long req = opts ? opts->chunk_len : 0;
-        if (int s = check_workspace(ctx, ws, ws_bytes, scan_large_workspace_bytes(T, d, m, batch, req, final_only))) return s;
+        const bool f32 = dtype == GOOM_C64;
+        const size_t need = f32 ? scan_large_workspace_bytes(T, d, m, batch, req, final_only) : scan_large_f64_workspace_bytes(T, d, m, batch, req, final_only);
+        if (int s = check_workspace(ctx, ws, ws_bytes, need)) return s;
         if (int s = need_ctx(ctx)) return s;
-        return run_scan_large(ctx, M, init, P, T, d, m, batch, req, ws, final_only);
+        return f32 ? run_scan_large(ctx, M, init, P, T, d, m, batch, req, ws, final_only)
+                   : run_scan_large_f64(ctx, M, init, P, T, d, m, batch, req, ws, final_only);
     }
     const ScanPlan p = plan_scan(T, d, d, m, batch, dtype, opts ? opts->chunk_len : 0, final_only);
     if (int s = check_workspace(ctx, ws, ws_bytes, p.total())) return s;
@@ -674,7 +675,8 @@ size_t goom_scan_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dty
     if (T <= 0 || d <= 0 || m <= 0 || batch <= 0 || d > GOOM_MAX_DIM_LMME || m > GOOM_MAX_DIM_LMME) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
     if (d > GOOM_MAX_DIM || m > GOOM_MAX_DIM)
-        return dtype == GOOM_C64 ? scan_large_workspace_bytes(T, d, m, batch, opts ? opts->chunk_len : 0, false) : 0;
+        return dtype == GOOM_C64 ? scan_large_workspace_bytes(T, d, m, batch, opts ? opts->chunk_len : 0, false)
+                                 : scan_large_f64_workspace_bytes(T, d, m, batch, opts ? opts->chunk_len : 0, false);
     ScanPlan p = plan_scan(T, d, d, m, batch, dtype, opts ? opts->chunk_len : 0, false);
     return p.total();
 }
@@ -684,7 +686,8 @@ size_t goom_reduce_workspace_bytes(int64_t T, int d, int m, int64_t batch, int d
     if (T <= 0 || d <= 0 || m <= 0 || batch <= 0 || d > GOOM_MAX_DIM_LMME || m > GOOM_MAX_DIM_LMME) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
     if (d > GOOM_MAX_DIM || m > GOOM_MAX_DIM)
-        return dtype == GOOM_C64 ? scan_large_workspace_bytes(T, d, m, batch, opts ? opts->chunk_len : 0, true) : 0;
+        return dtype == GOOM_C64 ? scan_large_workspace_bytes(T, d, m, batch, opts ? opts->chunk_len : 0, true)
+                                 : scan_large_f64_workspace_bytes(T, d, m, batch, opts ? opts->chunk_len : 0, true);
     ScanPlan p = plan_scan(T, d, d, m, batch, dtype, opts ? opts->chunk_len : 0, true);
     return p.total();
 }

@@ -132,6 +132,10 @@ int launch_chain256(goom_ctx *ctx, const void *M, const float *nrow, long long T
 size_t scan_large_workspace_bytes(long long T, int d, int m, long long batch, long long requested_chunk, bool final_only);
 int run_scan_large(goom_ctx *ctx, const void *M, const void *init, void *P, long long T, int d, int m, long long batch,
                    long long requested_chunk, void *ws, bool final_only);
+// the same for complex128 matrices
+size_t scan_large_f64_workspace_bytes(long long T, int d, int m, long long batch, long long requested_chunk, bool final_only);
+int run_scan_large_f64(goom_ctx *ctx, const void *M, const void *init, void *P, long long T, int d, int m, long long batch,
+                       long long requested_chunk, void *ws, bool final_only);
 int launch_lmme128(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int dtype);
 int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int n, int d, int m, int dtype);
 

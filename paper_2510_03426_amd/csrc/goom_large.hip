@@ -12,7 +12,7 @@
 // edge cases.
 #include <cmath>
 
-#include "goom_chain_kernel.h"
+#include "goom_large_scan.h"
 
 namespace {
 
@@ -229,234 +229,7 @@ __global__ __launch_bounds__(256) void lmme_store_kernel(const float *__restrict
 }
 
 
-// =====================================================================================
-// Scans of matrices above 128 x 128 (paper Section 4.1 runs chains up to 1024 x 1024).  The running
-// product of a chain is kept TRANSPOSED, St[column of the state][row], as float mantissas with one
-// power-of-two exponent per state column (double), so that one step,
-//     St <- St A~^T,  then every row of St rescaled (the row shifts of A~ folded in),
-// is the same NT GEMM plus two light passes, and closes under iteration.  All chains of a launch
-// (batch items x chunks) advance together, one step per round of launches.
-// =====================================================================================
-
-struct ChainGeom {
-    long long T, L;           // chain length, chunk length
-    long long chunks;         // chunks per batch item the launch covers (chain = item * chunks + chunk)
-    int d, dp;                // matrix size, padded to 128
-};
-
-// rows of M[b][chunk * L + s], scaled; a chain whose chunk has fewer than s + 1 steps gets the identity.
-// One wave per row (a row is at most 1024 entries: 16 per lane), four rows per workgroup:
-// grid (dp / 4, chains), 256 threads.
-__global__ __launch_bounds__(256) void chain_convert_left_kernel(const float2 *__restrict__ M, float *__restrict__ X, double *__restrict__ shifts,
-                                                                 ChainGeom q, long long s)
-{
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const long long chain = blockIdx.y, item = chain / q.chunks, chunk = chain % q.chunks;
-    const long long t = chunk * q.L + s;
-    const bool active = s < q.L && t < q.T;
-    float *xrow = X + ((size_t)chain * q.dp + row) * q.dp;
-    if (!active || row >= q.d) {
-        for (int j = lane; j < q.dp; j += 64) xrow[j] = (!active && j == row && row < q.d) ? 1.0f : 0.0f;
-        if (lane == 0) shifts[(size_t)chain * q.dp + row] = 0.0;
-        return;
-    }
-    const float2 *arow = M + (((size_t)item * q.T + t) * q.d + row) * q.d;
-    float2 e[16];
-    float mx = -__builtin_huge_valf();
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int j = lane + 64 * r;
-        e[r] = float2{-__builtin_huge_valf(), 0.0f};
-        if (j < q.d) e[r] = arow[j];
-        mx = fmaxf(mx, e[r].x);
-    }
-#pragma unroll
-    for (int sft = 32; sft >= 1; sft >>= 1) mx = fmaxf(mx, __shfl_xor(mx, sft, 64));
-    const bool zero_row = !(mx > -__builtin_huge_valf());
-    const float sh = zero_row ? 0.0f : ceilf(mx * kLog2eF);
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int j = lane + 64 * r;
-        if (j < q.dp) xrow[j] = (j < q.d && !zero_row) ? signed_scaled(e[r].x, e[r].y, sh) : 0.0f;
-    }
-    if (lane == 0) shifts[(size_t)chain * q.dp + row] = (double)sh;
-}
-
-// Row n of the product (state column n): out[n][i] = in[n][i] 2^(shift_i - s_n) with s_n the largest
-// exponent of in[n][i] 2^shift_i, and the column's exponent grows by s_n.  shifts: [.][len] doubles with
-// stride shift_stride per chain (0: the same vector for all), or NULL for none.  One wave per row
-// (len <= 1024), four rows per workgroup: grid (rows / 4, chains), 256 threads; in and out may be the
-// same buffer.
-__global__ __launch_bounds__(256) void rescale_rows_kernel(const float *in, float *out, const double *__restrict__ shifts, long long shift_stride,
-                                                           double *__restrict__ expo, int rows_padded, int len)
-{
-    const int lane = threadIdx.x & 63;
-    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const long long chain = blockIdx.y;
-    const float *src = in + ((size_t)chain * rows_padded + n) * len;
-    float *dst = out + ((size_t)chain * rows_padded + n) * len;
-    const double *sh = shifts ? shifts + (size_t)chain * shift_stride : nullptr;
-    // shifts relative to their largest, so that they fit float arithmetic next to the entries' exponents
-    double smax = sh ? -1.0e300 : 0.0;
-    if (sh)
-        for (int i = lane; i < len; i += 64) smax = fmax(smax, sh[i]);
-#pragma unroll
-    for (int sft = 32; sft >= 1; sft >>= 1) smax = fmax(smax, __shfl_xor(smax, sft, 64));
-    float v[16], rel[16];
-    float mx = -1.0e30f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int i = lane + 64 * r;
-        v[r] = 0.0f;
-        rel[r] = 0.0f;
-        if (i < len) {
-            v[r] = src[i];
-            const double dr = sh ? sh[i] - smax : 0.0;
-            rel[r] = dr > -4000.0 ? (float)dr : -4000.0f;
-            if (v[r] != 0.0f) mx = fmaxf(mx, CF::exponent_of(v[r]) + rel[r]);
-        }
-    }
-#pragma unroll
-    for (int sft = 32; sft >= 1; sft >>= 1) mx = fmaxf(mx, __shfl_xor(mx, sft, 64));
-    const bool all_zero = !(mx > -1.0e29f);
-    const float sn = all_zero ? 0.0f : mx;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int i = lane + 64 * r;
-        if (i < len) dst[i] = __builtin_ldexpf(v[r], (int)CF::clamp_shift(rel[r] - sn));
-    }
-    if (lane == 0) {
-        double &e = expo[(size_t)chain * rows_padded + n];
-        e = all_zero ? 0.0 : e + smax + (double)sn;
-    }
-}
-
-// The carry phase's pass between two products: from the raw product in[n][i] (state column n, exponent
-// ein[n]) it writes (B) the state itself, rows normalised, where the scan wants it kept, and / or (A) the
-// state with the exponents of the next left factor's columns folded onto its rows (shifts[i]), ready to be
-// multiplied.  One wave per row, four rows per workgroup: grid (rows / 4, batch), 256 threads.
-struct CarryPass {
-    const float *in; const double *ein; long long in_stride, ein_stride;
-    float *outA; double *eA; long long outA_stride, eA_stride; const double *shifts; long long shift_stride;
-    float *outB; double *eB; long long outB_stride, eB_stride;
-    int rows_padded, len;
-};
-__global__ __launch_bounds__(256) void carry_pass_kernel(CarryPass p)
-{
-    const int lane = threadIdx.x & 63;
-    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const long long b = blockIdx.y;
-    const float *src = p.in + b * p.in_stride + (size_t)n * p.len;
-    const double e0 = p.ein[b * p.ein_stride + n];
-    float v[16];
-    float mxB = -1.0e30f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int i = lane + 64 * r;
-        v[r] = i < p.len ? src[i] : 0.0f;
-        if (v[r] != 0.0f) mxB = fmaxf(mxB, CF::exponent_of(v[r]));
-    }
-#pragma unroll
-    for (int sft = 32; sft >= 1; sft >>= 1) mxB = fmaxf(mxB, __shfl_xor(mxB, sft, 64));
-    const bool all_zero = !(mxB > -1.0e29f);
-    if (p.outB) {
-        float *dst = p.outB + b * p.outB_stride + (size_t)n * p.len;
-        const int sh = all_zero ? 0 : -(int)mxB;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int i = lane + 64 * r;
-            if (i < p.len) dst[i] = __builtin_ldexpf(v[r], sh);
-        }
-        if (lane == 0) p.eB[b * p.eB_stride + n] = all_zero ? 0.0 : e0 + (double)mxB;
-    }
-    if (p.outA) {
-        const double *sh = p.shifts + b * p.shift_stride;
-        double smax = -1.0e300;
-        for (int i = lane; i < p.len; i += 64) smax = fmax(smax, sh[i]);
-#pragma unroll
-        for (int sft = 32; sft >= 1; sft >>= 1) smax = fmax(smax, __shfl_xor(smax, sft, 64));
-        float rel[16];
-        float mxA = -1.0e30f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int i = lane + 64 * r;
-            rel[r] = 0.0f;
-            if (i < p.len) {
-                const double dr = sh[i] - smax;
-                rel[r] = dr > -4000.0 ? (float)dr : -4000.0f;
-                if (v[r] != 0.0f) mxA = fmaxf(mxA, CF::exponent_of(v[r]) + rel[r]);
-            }
-        }
-#pragma unroll
-        for (int sft = 32; sft >= 1; sft >>= 1) mxA = fmaxf(mxA, __shfl_xor(mxA, sft, 64));
-        const bool zeroA = !(mxA > -1.0e29f);
-        const float sn = zeroA ? 0.0f : mxA;
-        float *dst = p.outA + b * p.outA_stride + (size_t)n * p.len;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int i = lane + 64 * r;
-            if (i < p.len) dst[i] = __builtin_ldexpf(v[r], (int)CF::clamp_shift(rel[r] - sn));
-        }
-        if (lane == 0) p.eA[b * p.eA_stride + n] = zeroA ? 0.0 : e0 + smax + (double)sn;
-    }
-}
-
-// St = identity (first d rows and columns), exponents 0.  grid (rows_padded, chains), 256 threads.
-__global__ __launch_bounds__(256) void state_identity_kernel(float *St, double *expo, int rows_padded, int len, int d)
-{
-    const int n = blockIdx.x;
-    const long long chain = blockIdx.y;
-    float *row = St + ((size_t)chain * rows_padded + n) * len;
-    for (int i = threadIdx.x; i < len; i += 256) row[i] = (i == n && n < d) ? 1.0f : 0.0f;
-    if (threadIdx.x == 0) expo[(size_t)chain * rows_padded + n] = 0.0;
-}
-
-// out[b][j][i] = in[b][i][j], square dp x dp.  grid (dp / 32, dp / 32, batch), block 32 x 8.
-__global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ in, long long in_stride, float *__restrict__ out, long long out_stride,
-                                                        int dp)
-{
-    __shared__ float tile[32][33];
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    const int i0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
-    const long long b = blockIdx.z;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) tile[ty + 8 * r][tx] = in[b * in_stride + (size_t)(i0 + ty + 8 * r) * dp + j0 + tx];
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < 4; ++r) out[b * out_stride + (size_t)(j0 + ty + 8 * r) * dp + i0 + tx] = tile[tx][ty + 8 * r];
-}
-
-// P[b][t][i][n] = GOOM of St[chain][n][i] 2^(expo[chain][n]), t = chunk * L + s (or slot `fixed_slot`
-// of a [b][slots] array when fixed_slot >= 0); chains without that step store nothing.
-// grid (ceil(d / 32), ceil(m / 32), chains), block 32 x 8.
-__global__ __launch_bounds__(256) void chain_store_kernel(const float *__restrict__ St, const double *__restrict__ expo, float2 *__restrict__ P,
-                                                          ChainGeom q, long long s, int m, int rows_padded, long long slots, long long fixed_slot)
-{
-    __shared__ float tile[32][33];
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    const int i0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
-    const long long chain = blockIdx.z, item = chain / q.chunks, chunk = chain % q.chunks;
-    const long long t = chunk * q.L + s;
-    if (fixed_slot < 0 && !(s < q.L && t < q.T)) return;
-    const long long slot = fixed_slot >= 0 ? fixed_slot : t;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) tile[ty + 8 * r][tx] = St[((size_t)chain * rows_padded + n0 + ty + 8 * r) * q.dp + i0 + tx]; // [n][i]
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int i = i0 + ty + 8 * r, n = n0 + tx;
-        if (i < q.d && n < m) {
-            const float x = tile[tx][ty + 8 * r];
-            float2 o;
-            o.x = x != 0.0f ? CF::out_re((float)x, 0.0f, expo[(size_t)chain * rows_padded + n]) : -__builtin_huge_valf();
-            o.y = x < 0.0f ? CF::pi() : 0.0f;
-            P[(((size_t)item * slots + slot) * q.d + i) * m + n] = o;
-        }
-    }
-}
-
-inline int pad_to(int v, int a) { return (v + a - 1) / a * a; }
+using goom_large::pad_to;
 
 } // namespace
 
@@ -507,59 +280,32 @@ int launch_lmme_large(goom_ctx *ctx, const void *A, const void *B, void *C, long
 } // namespace goom
 
 // ------------------------------------------------------------------------------------------------
-// Scan / reduction driver for matrices above 128 x 128: the three phases of the chunked scan, every
-// phase advancing all of its chains by one step per round of launches.
+// Scans and reductions of complex64 matrices above 128 x 128: the shared driver with this file's GEMM, the
+// conversion of an initial state, and the register-resident kernels for 128 < d <= 256.
 // ------------------------------------------------------------------------------------------------
 namespace {
 
-struct LargePlan {
-    long long L, C, C1; // chunk length, chunks per item, chunks whose products phase 1 forms
-    int dp, mp;
-    size_t off_atil, off_na, off_s1, off_e1, off_s3, off_e3, off_cbuf, off_yt, off_ey, off_trow, off_nrow, off_x2, off_ey2, total;
-    bool resident; // 128 < d <= 256 and m <= 256: the chains run with register-resident states
-};
-
-LargePlan plan_large(long long T, int d, int m, long long batch, long long requested, bool final_only)
-{
-    LargePlan p;
-    p.dp = pad_to(d, 128);
-    p.mp = pad_to(m, 128);
-    const long long tiles = (long long)(p.dp / 128) * (p.dp / 128);
-    const size_t per_chain = ((size_t)4 * p.dp * p.dp + (size_t)2 * p.mp * p.dp) * 4;
-    long long c;
-    if (requested > 0) {
-        c = (T + requested - 1) / requested;
-    } else {
-        const long long c_par = (512 + batch * tiles - 1) / (batch * tiles); // enough tiles to fill the chip
-        const long long c_depth = (long long)std::ceil(std::sqrt(2.0 * (double)T));
-        c = c_par < c_depth ? c_par : c_depth;
-        const long long c_mem = (long long)((size_t)8 << 30) / (long long)(per_chain * (size_t)batch);
-        if (c > c_mem) c = c_mem;
+struct OpsF32 {
+    static constexpr bool kResident = true;
+    static int prepare(goom_ctx *) { return GOOM_OK; }
+    static void gemm(hipStream_t st, const float *X, const float *Y, float *C, unsigned gx, unsigned gy, unsigned gz, int M, int N, int K,
+                     long long sx, long long sy, long long sc)
+    {
+        hipLaunchKernelGGL(gemm_nt_kernel, dim3(gx, gy, gz), dim3(256), 0, st, X, Y, C, M, N, K, sx, sy, sc);
     }
-    if (c < 1) c = 1;
-    p.L = (T + c - 1) / c;
-    p.C = (T + p.L - 1) / p.L;
-    p.C1 = p.C <= 1 ? 0 : (final_only ? p.C : p.C - 1);
-    const size_t chains = (size_t)batch * p.C;
-    size_t off = 0;
-    auto take = [&](size_t bytes) { size_t o = off; off += goom::align_up(bytes, 256); return o; };
-    p.off_atil = take(chains * p.dp * p.dp * 4);
-    p.off_na = take(chains * p.dp * 8);
-    p.off_s1 = take((size_t)batch * p.C1 * p.dp * p.dp * 4);
-    p.off_e1 = take((size_t)batch * p.C1 * p.dp * 8);
-    p.off_s3 = take(final_only ? 0 : chains * p.mp * p.dp * 4);
-    p.off_e3 = take(final_only ? 0 : chains * p.mp * 8);
-    p.off_cbuf = take(chains * (size_t)(p.mp > p.dp ? p.mp : p.dp) * p.dp * 4);
-    p.off_yt = take((size_t)batch * p.mp * p.dp * 4);
-    p.off_ey = take((size_t)batch * p.mp * 8);
-    p.off_trow = take((size_t)batch * (p.C1 > 0 ? p.C1 : 1) * p.dp * p.dp * 4); // chunk products, transposed back
-    p.off_x2 = take((size_t)batch * p.mp * p.dp * 4); // carry phase: the operand of the next product and its exponents
-    p.off_ey2 = take((size_t)batch * p.mp * 8);
-    p.resident = p.dp == 256 && p.mp <= 256;
-    p.off_nrow = take(p.resident ? (size_t)batch * T * 256 * 4 : 0);
-    p.total = off;
-    return p;
-}
+    static void init_state(hipStream_t st, const void *init, double *ey, float *yt, int d, int m, int mp, int dp, unsigned batch)
+    {
+        hipLaunchKernelGGL(column_shift_kernel<double>, dim3(mp / 64, batch), dim3(256), 0, st, static_cast<const float2 *>(init), ey, d, m, mp);
+        hipLaunchKernelGGL(convert_right_kernel<double>, dim3(mp / 32, dp / 32, batch), dim3(256), 0, st, static_cast<const float2 *>(init), ey, yt, d,
+                           m, mp, dp);
+    }
+    static int row_shifts(goom_ctx *ctx, const void *M, float *nrow, int d, long long nmat) { return goom::launch_row_shifts256(ctx, M, nrow, d, nmat); }
+    static int chains(goom_ctx *ctx, const void *M, const float *nrow, long long T, long long L, long long chunks, long long batch, int d, int m,
+                      const float *init, const double *einit, float *fin, double *efin, void *P)
+    {
+        return goom::launch_chain256(ctx, M, nrow, T, L, chunks, batch, d, m, init, einit, fin, efin, P);
+    }
+};
 
 } // namespace
 
@@ -567,134 +313,13 @@ namespace goom {
 
 size_t scan_large_workspace_bytes(long long T, int d, int m, long long batch, long long requested_chunk, bool final_only)
 {
-    return plan_large(T, d, m, batch, requested_chunk, final_only).total;
+    return goom_large::plan_large(T, d, m, batch, requested_chunk, final_only, sizeof(float), true).total;
 }
 
 int run_scan_large(goom_ctx *ctx, const void *M, const void *init, void *P, long long T, int d, int m, long long batch,
                    long long requested_chunk, void *ws, bool final_only)
 {
-    const LargePlan p = plan_large(T, d, m, batch, requested_chunk, final_only);
-    const long long chains_all = batch * p.C;
-    if (chains_all > 65535) return fail(ctx, GOOM_EUNSUPPORTED, "too many chains (%lld) for matrices above %d", chains_all, GOOM_MAX_DIM);
-    unsigned char *w = static_cast<unsigned char *>(ws);
-    float *atil = reinterpret_cast<float *>(w + p.off_atil);
-    double *na = reinterpret_cast<double *>(w + p.off_na);
-    float *s1 = reinterpret_cast<float *>(w + p.off_s1);
-    double *e1 = reinterpret_cast<double *>(w + p.off_e1);
-    float *s3 = reinterpret_cast<float *>(w + p.off_s3);
-    double *e3 = reinterpret_cast<double *>(w + p.off_e3);
-    float *cbuf = reinterpret_cast<float *>(w + p.off_cbuf);
-    float *yt = reinterpret_cast<float *>(w + p.off_yt);
-    double *ey = reinterpret_cast<double *>(w + p.off_ey);
-    float *trow = reinterpret_cast<float *>(w + p.off_trow);
-    float *cbuf2 = reinterpret_cast<float *>(w + p.off_x2);
-    double *ey2 = reinterpret_cast<double *>(w + p.off_ey2);
-    const float2 *Mg = static_cast<const float2 *>(M);
-    const int dp = p.dp, mp = p.mp;
-    hipStream_t st = ctx->stream;
-    auto ok = [&](const char *what) { return check_hip(ctx, hipGetLastError(), what); };
-
-    // one step of all chains of a launch: state[chain] (rows x dp) <- state A~^T, rescaled
-    auto advance = [&](float *state, double *expo, int rows, const ChainGeom &q, long long chains, long long s) {
-        hipLaunchKernelGGL(chain_convert_left_kernel, dim3(dp / 4, (unsigned)chains), dim3(256), 0, st, Mg, atil, na, q, s);
-        hipLaunchKernelGGL(gemm_nt_kernel, dim3(dp / BN, rows / BM, (unsigned)chains), dim3(256), 0, st, state, atil, cbuf, rows, dp, dp,
-                           (long long)rows * dp, (long long)dp * dp, (long long)rows * dp);
-        hipLaunchKernelGGL(rescale_rows_kernel, dim3(rows / 4, (unsigned)chains), dim3(256), 0, st, cbuf, state, na, (long long)dp, expo, rows, dp);
-    };
-
-    float *nrow = reinterpret_cast<float *>(w + p.off_nrow);
-    if (p.resident) {
-        prof_begin(ctx, "scan_large_row_shifts");
-        const int e = launch_row_shifts256(ctx, M, nrow, d, batch * T);
-        prof_end(ctx);
-        if (e) return e;
-    }
-
-    // ---- phase 1: chunk products
-    if (p.C1 > 0) {
-        ChainGeom q{T, p.L, p.C1, d, dp};
-        const long long chains = batch * p.C1;
-        prof_begin(ctx, "scan_large_phase1_chunk_products");
-        if (p.resident) {
-            if (int e = launch_chain256(ctx, M, nrow, T, p.L, p.C1, batch, d, d, nullptr, nullptr, s1, e1, nullptr)) return e;
-        } else {
-            hipLaunchKernelGGL(state_identity_kernel, dim3(dp, (unsigned)chains), dim3(256), 0, st, s1, e1, dp, dp, d);
-            for (long long s = 0; s < p.L; ++s) advance(s1, e1, dp, q, chains, s);
-        }
-        prof_end(ctx);
-        if (int e = ok("scan_large phase 1")) return e;
-    }
-
-    // ---- phase 2: prefixes at the chunk boundaries (and, for a reduction, the final product)
-    prof_begin(ctx, "scan_large_phase2_carries");
-    if (init) {
-        hipLaunchKernelGGL(column_shift_kernel<double>, dim3(mp / 64, (unsigned)batch), dim3(256), 0, st, static_cast<const float2 *>(init), ey, d, m, mp);
-        hipLaunchKernelGGL(convert_right_kernel<double>, dim3(mp / 32, dp / 32, (unsigned)batch), dim3(256), 0, st, static_cast<const float2 *>(init),
-                           ey, yt, d, m, mp, dp);
-    } else {
-        hipLaunchKernelGGL(state_identity_kernel, dim3(mp, (unsigned)batch), dim3(256), 0, st, yt, ey, mp, dp, d);
-    }
-    // Y <- T_c Y for c = 0, 1, ...: the exponents of T_c's columns go onto Y's rows, T_c (held transposed, as a
-    // state) is turned K-contiguous again; two launches per chunk.  The scan keeps every Y (the carry into chunk c).
-    if (p.C1 > 0)
-        hipLaunchKernelGGL(transpose_kernel, dim3(dp / 32, dp / 32, (unsigned)(batch * p.C1)), dim3(256), 0, st, s1, (long long)dp * dp, trow,
-                           (long long)dp * dp, dp);
-    auto pass = [&](const float *in, const double *ein, long long c_next) {
-        // from `in`: the carry into chunk c_next (kept, for a scan) and the operand of the product with T_c_next
-        CarryPass cp;
-        cp.in = in; cp.ein = ein; cp.in_stride = (long long)mp * dp; cp.ein_stride = (long long)mp;
-        const bool more = c_next < p.C1;
-        cp.outA = more ? cbuf2 : nullptr; cp.eA = ey2; cp.outA_stride = (long long)mp * dp; cp.eA_stride = (long long)mp;
-        cp.shifts = more ? e1 + (size_t)c_next * dp : nullptr; cp.shift_stride = (long long)p.C1 * dp;
-        const bool keep = !final_only;
-        cp.outB = keep ? s3 + (size_t)c_next * mp * dp : (more ? nullptr : yt);
-        cp.eB = keep ? e3 + (size_t)c_next * mp : ey;
-        cp.outB_stride = keep ? (long long)p.C * mp * dp : (long long)mp * dp;
-        cp.eB_stride = keep ? (long long)p.C * mp : (long long)mp;
-        cp.rows_padded = mp; cp.len = dp;
-        if (cp.outA || cp.outB) hipLaunchKernelGGL(carry_pass_kernel, dim3(mp / 4, (unsigned)batch), dim3(256), 0, st, cp);
-    };
-    pass(yt, ey, 0);
-    for (long long c = 0; c < p.C1; ++c) {
-        hipLaunchKernelGGL(gemm_nt_kernel, dim3(dp / BN, mp / BM, (unsigned)batch), dim3(256), 0, st, cbuf2, trow + (size_t)c * dp * dp, cbuf, mp, dp, dp,
-                           (long long)mp * dp, (long long)p.C1 * dp * dp, (long long)mp * dp);
-        pass(cbuf, ey2, c + 1);
-    }
-    if (final_only && p.C1 > 0) {
-        ChainGeom q{T, p.L, 1, d, dp};
-        hipLaunchKernelGGL(chain_store_kernel, dim3((d + 31) / 32, (m + 31) / 32, (unsigned)batch), dim3(256), 0, st, yt, ey, static_cast<float2 *>(P), q,
-                           0LL, m, mp, 1LL, 0LL);
-    }
-    prof_end(ctx);
-    if (int e = ok("scan_large phase 2")) return e;
-    if (final_only && p.C1 > 0) return GOOM_OK;
-
-    // ---- phase 3: every chunk from its incoming prefix, all prefixes stored (a single chunk runs only this)
-    {
-        ChainGeom q{T, p.L, p.C, d, dp};
-        float *state = final_only ? yt : s3; // a reduction of a single chunk walks it here
-        double *expo = final_only ? ey : e3;
-        prof_begin(ctx, final_only ? "scan_large_single_chunk" : "scan_large_phase3_outputs");
-        if (p.resident) {
-            // (a reduction of a single chunk leaves its product in the state, stored below)
-            const int e = final_only ? launch_chain256(ctx, M, nrow, T, p.L, p.C, batch, d, m, state, expo, state, expo, nullptr)
-                                     : launch_chain256(ctx, M, nrow, T, p.L, p.C, batch, d, m, state, expo, nullptr, nullptr, P);
-            if (e) return e;
-        }
-        for (long long s = 0; s < (p.resident ? 0 : p.L); ++s) {
-            advance(state, expo, mp, q, chains_all, s);
-            if (!final_only)
-                hipLaunchKernelGGL(chain_store_kernel, dim3((d + 31) / 32, (m + 31) / 32, (unsigned)chains_all), dim3(256), 0, st, state, expo,
-                                   static_cast<float2 *>(P), q, s, m, mp, T, -1LL);
-        }
-        if (final_only) {
-            ChainGeom q1{T, p.L, 1, d, dp};
-            hipLaunchKernelGGL(chain_store_kernel, dim3((d + 31) / 32, (m + 31) / 32, (unsigned)batch), dim3(256), 0, st, state, expo,
-                               static_cast<float2 *>(P), q1, 0LL, m, mp, 1LL, 0LL);
-        }
-        prof_end(ctx);
-    }
-    return ok("scan_large phase 3");
+    return goom_large::run_scan_large_t<float, OpsF32>(ctx, M, init, P, T, d, m, batch, requested_chunk, ws, final_only);
 }
 
 } // namespace goom

@@ -6,9 +6,10 @@
 //   3. C~^T = B~^T A~^T on the double-precision matrix instruction (16 x 16 x 4): 128 x 128 tile per
 //      workgroup, 64 x 64 per wave, K in steps of 16 through double-buffered LDS;
 //   4. signed logarithm, shifts re-added, transposed back on the way out.
+// Scans and reductions of such matrices (Section 4.1) run through the shared driver with this file's GEMM.
 #include <cmath>
 
-#include "goom_chain_kernel.h"
+#include "goom_large_scan.h"
 
 namespace {
 
@@ -233,7 +234,7 @@ __global__ __launch_bounds__(256) void lmme_store_f64_kernel(const double *__res
     }
 }
 
-inline int pad_to(int v, int a) { return (v + a - 1) / a * a; }
+using goom_large::pad_to;
 
 } // namespace
 
@@ -282,6 +283,50 @@ int launch_lmme_large_f64(goom_ctx *ctx, const void *A, const void *B, void *C, 
                        static_cast<double2 *>(C), n, m, Np, Mp);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch lmme_store_f64_kernel");
+}
+
+} // namespace goom
+
+// ------------------------------------------------------------------------------------------------
+// Scans and reductions of complex128 matrices above 128 x 128
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+constexpr size_t kGemmLds = (size_t)2 * (BM + BN) * LDK * sizeof(double);
+
+struct OpsF64 {
+    static constexpr bool kResident = false;
+    static int prepare(goom_ctx *ctx)
+    {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_nt_f64_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLds);
+        return e == hipSuccess ? GOOM_OK : goom::check_hip(ctx, e, "hipFuncSetAttribute(gemm_nt_f64_kernel)");
+    }
+    static void gemm(hipStream_t st, const double *X, const double *Y, double *C, unsigned gx, unsigned gy, unsigned gz, int M, int N, int K,
+                     long long sx, long long sy, long long sc)
+    {
+        hipLaunchKernelGGL(gemm_nt_f64_kernel, dim3(gx, gy, gz), dim3(256), kGemmLds, st, X, Y, C, M, N, K, sx, sy, sc);
+    }
+    static void init_state(hipStream_t st, const void *init, double *ey, double *yt, int d, int m, int mp, int dp, unsigned batch)
+    {
+        hipLaunchKernelGGL(column_shift_f64_kernel, dim3(mp / 64, batch), dim3(256), 0, st, static_cast<const double2 *>(init), ey, d, m, mp);
+        hipLaunchKernelGGL(convert_right_f64_kernel, dim3(mp / 32, dp / 32, batch), dim3(256), 0, st, static_cast<const double2 *>(init), ey, yt, d, m,
+                           mp, dp);
+    }
+};
+
+} // namespace
+
+namespace goom {
+
+size_t scan_large_f64_workspace_bytes(long long T, int d, int m, long long batch, long long requested_chunk, bool final_only)
+{
+    return goom_large::plan_large(T, d, m, batch, requested_chunk, final_only, sizeof(double), false).total;
+}
+
+int run_scan_large_f64(goom_ctx *ctx, const void *M, const void *init, void *P, long long T, int d, int m, long long batch,
+                       long long requested_chunk, void *ws, bool final_only)
+{
+    return goom_large::run_scan_large_t<double, OpsF64>(ctx, M, init, P, T, d, m, batch, requested_chunk, ws, final_only);
 }
 
 } // namespace goom
