@@ -67,7 +67,7 @@ typedef enum goom_dtype {
 
 /* largest matrix dimension of the register-resident kernels (scans, recurrences, small products) */
 #define GOOM_MAX_DIM 128
-/* largest dimension of goom_lmme (both formats) and of scans of complex64 matrices: above GOOM_MAX_DIM the
+/* largest dimension of goom_lmme, goom_scan and goom_reduce (both formats): above GOOM_MAX_DIM the
  * product runs as scaled operands, a tiled GEMM and a store pass through the workspace (the paper's experiments
  * go up to 1024) */
 #define GOOM_MAX_DIM_LMME 1024
