@@ -151,7 +151,8 @@ typedef struct goom_scan_opts {
  *     P[b, 0] = LMME(M[b, 0], init[b])      (or M[b, 0] itself when init is NULL)
  *     P[b, t] = LMME(M[b, t], P[b, t-1])
  * M: [batch, T, d, d]; init: NULL or [batch, d, m] (m != d allowed, e.g. a vector u_0,
- * m = 1); P: [batch, T, d, m] (m = d when init is NULL).  opts may be NULL.
+ * m = 1); P: [batch, T, d, m] (m = d when init is NULL); 1 <= d, m <= GOOM_MAX_DIM_LMME, both
+ * formats.  opts may be NULL.
  * The chain is cut into chunks: phase 1 multiplies each chunk down to one matrix,
  * phase 2 scans those chunk products, phase 3 re-walks every chunk from its incoming
  * prefix and writes all outputs.  Between steps the running product is kept as real
