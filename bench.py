@@ -199,6 +199,12 @@ def main():
         gsec = timed(torch, lambda: torch.mm(ga, gb), 5)
         result["sgemm_tflops_measured"] = round(2 * 8192.0 ** 3 / gsec / 1e12, 1)
         del ga, gb
+        # and for a kernel that issues nothing but 16 x 16 x 4 matrix instructions (the library's probe)
+        sink = torch.zeros(4, device=dev)
+        for name, dbl in (("mfma_f32_tflops_measured", False), ("mfma_f64_tflops_measured", True)):
+            its = 4096
+            msec = timed(torch, lambda: g.probe_matrix_unit(sink, its, dbl), 3)
+            result[name] = round(g.PROBE_MATRIX_FLOP_PER_ITER * its / msec / 1e12, 1)
 
     # ---- the other workloads of the same path, each timed on its own (not part of `value`)
     if not args.no_extras and not args.basic_extras:

@@ -115,6 +115,14 @@ int goom_profile_get(goom_ctx *ctx, int i, const char **label, float *millisecon
 #define GOOM_PROBE_COPY 2
 int goom_probe_bandwidth(goom_ctx *ctx, const void *a, void *b, size_t bytes, int mode);
 
+/* What the matrix units sustain when a kernel issues nothing else (measurement aid): enqueues a kernel of
+ * 2048 workgroups x 4 waves, each wave issuing 8 x `iters` 16 x 16 x 4 matrix instructions (2048 flop each)
+ * in the component type of `dtype` (float for GOOM_C64, double for GOOM_C128) on independent accumulators:
+ * GOOM_PROBE_MATRIX_FLOP_PER_ITER x iters flop in all.  sink: at least 4 bytes of device memory (never
+ * written in practice).  The caller times it on the context's stream. */
+#define GOOM_PROBE_MATRIX_FLOP_PER_ITER 134217728LL /* 2048 workgroups x 4 waves x 8 instructions x 2048 flop */
+int goom_probe_matrix_unit(goom_ctx *ctx, void *sink, int64_t iters, int dtype);
+
 /* ---- codecs (paper Section 3.1) -------------------------------------------------- */
 
 /* Real floats -> GOOMs: y[i] = (log|x[i]|, x[i] < 0 ? pi : 0).  x: n floats (GOOM_C64)

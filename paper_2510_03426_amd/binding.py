@@ -22,7 +22,7 @@ AFFINE_TIME_INVARIANT = 1
 
 EXPORTS = [
     "goom_version", "goom_create", "goom_destroy", "goom_set_stream", "goom_last_error",
-    "goom_status_name", "goom_probe_bandwidth", "goom_profile_enable", "goom_profile_count", "goom_profile_get", "goom_to_goom", "goom_from_goom", "goom_lmme", "goom_lmme_workspace_bytes",
+    "goom_status_name", "goom_probe_bandwidth", "goom_probe_matrix_unit", "goom_profile_enable", "goom_profile_count", "goom_profile_get", "goom_to_goom", "goom_from_goom", "goom_lmme", "goom_lmme_workspace_bytes",
     "goom_scan", "goom_scan_workspace_bytes", "goom_reduce", "goom_reduce_workspace_bytes",
     "goom_scan_real", "goom_scan_real_workspace_bytes", "goom_reduce_real", "goom_reduce_real_workspace_bytes",
     "goom_scan_reset", "goom_scan_reset_workspace_bytes", "goom_lyapunov_spectrum",
@@ -107,6 +107,7 @@ def load_library():
     lib.goom_affine_scan_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_affine_scan_workspace_bytes.restype = sz
     lib.goom_probe_bandwidth.argtypes = [vp, vp, vp, sz, i32]
+    lib.goom_probe_matrix_unit.argtypes = [vp, vp, i64, i32]
     lib.goom_affine_scan_scaled.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
     lib.goom_affine_scan_scaled_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_affine_scan_scaled_workspace_bytes.restype = sz
@@ -183,6 +184,13 @@ class Goom:
         """One streaming pass (0 read a, 1 fill b, 2 copy a to b) on the context's stream; the caller times it."""
         nbytes = b.numel() * b.element_size()
         self._check(self.lib.goom_probe_bandwidth(self._ctx, _ptr(a), _ptr(b), nbytes, mode))
+
+    PROBE_MATRIX_FLOP_PER_ITER = 134217728
+
+    def probe_matrix_unit(self, sink, iters: int, double: bool = False):
+        """A kernel of nothing but matrix instructions (PROBE_MATRIX_FLOP_PER_ITER * iters flop) on the context's
+        stream; sink: a device tensor of at least 4 bytes; the caller times it."""
+        self._check(self.lib.goom_probe_matrix_unit(self._ctx, _ptr(sink), iters, 1 if double else 0))
 
     def profile_enable(self, on: bool = True):
         self._check(self.lib.goom_profile_enable(self._ctx, int(on)))

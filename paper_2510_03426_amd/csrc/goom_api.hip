@@ -587,6 +587,15 @@ int goom_probe_bandwidth(goom_ctx *ctx, const void *a, void *b, size_t bytes, in
     return launch_probe(ctx, a, b, bytes, mode);
 }
 
+int goom_probe_matrix_unit(goom_ctx *ctx, void *sink, int64_t iters, int dtype)
+{
+    if (int s = check_common(ctx, dtype)) return s;
+    if (!sink || !aligned(sink, 4)) return fail(ctx, GOOM_EINVAL, "the probe wants 4 bytes of device memory");
+    if (iters <= 0 || iters > (1LL << 24)) return fail(ctx, GOOM_EINVAL, "iters must be in 1 ... 2^24 (%lld)", (long long)iters);
+    if (int s = need_ctx(ctx)) return s;
+    return launch_matrix_probe(ctx, sink, iters, dtype);
+}
+
 int goom_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, uint32_t flags)
 {
     if (int s = check_common(ctx, dtype)) return s;

@@ -328,6 +328,41 @@ template <int MODE> __global__ __launch_bounds__(256) void probe_kernel(const pf
 }
 } // namespace
 
+// ---- matrix-unit probe: nothing but 16 x 16 x 4 matrix instructions on eight independent accumulators
+namespace {
+typedef double pd4 __attribute__((ext_vector_type(4)));
+// (second launch bound, double only: at two waves per SIMD the compiler keeps the accumulators in ordinary
+// registers; with the whole register file to itself it parks them in the accumulation registers and copies all
+// of them back and forth in every iteration, which costs the double-precision loop a third of its rate; the
+// float loop is 3 % faster the other way round)
+template <typename R, typename V> __global__ __launch_bounds__(256, sizeof(R) == 8 ? 2 : 1) void matrix_probe_kernel(float *sink, long long iters)
+{
+    V acc[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u] = V{0, 0, 0, 0};
+    const R x = (R)(threadIdx.x & 3) * (R)0.25, y = (R)(threadIdx.x & 7) * (R)0.125;
+    for (long long i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if constexpr (sizeof(R) == 4) acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(x, y, acc[u], 0, 0, 0);
+            else acc[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(x, y, acc[u], 0, 0, 0);
+        }
+    }
+    R t = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t += acc[u][0] + acc[u][1] + acc[u][2] + acc[u][3];
+    if (t == (R)-1.2345) sink[0] = 1.0f; // never true: the sums are non-negative
+}
+} // namespace
+
+int launch_matrix_probe(goom_ctx *ctx, void *sink, long long iters, int dtype)
+{
+    // 2048 workgroups of four waves: two waves on every SIMD of the chip
+    if (dtype == GOOM_C64) hipLaunchKernelGGL((matrix_probe_kernel<float, pf4>), dim3(2048), dim3(256), 0, ctx->stream, static_cast<float *>(sink), iters);
+    else hipLaunchKernelGGL((matrix_probe_kernel<double, pd4>), dim3(2048), dim3(256), 0, ctx->stream, static_cast<float *>(sink), iters);
+    return check_hip(ctx, hipGetLastError(), "launch matrix_probe_kernel");
+}
+
 int launch_probe(goom_ctx *ctx, const void *a, void *b, size_t bytes, int mode)
 {
     const size_t n = bytes / 16;

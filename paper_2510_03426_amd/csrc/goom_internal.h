@@ -143,6 +143,7 @@ int launch_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, u
 int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype);
 int launch_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, size_t n, int dtype);
 int launch_probe(goom_ctx *ctx, const void *a, void *b, size_t bytes, int mode);
+int launch_matrix_probe(goom_ctx *ctx, void *sink, long long iters, int dtype);
 int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t nvec, int d, int dtype);
 
 } // namespace goom

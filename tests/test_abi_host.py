@@ -91,6 +91,9 @@ def test_argument_validation_without_device(lib):
     assert lib.goom_probe_bandwidth(None, p, p, 100, 0) == EINVAL
     assert lib.goom_probe_bandwidth(None, None, p, 1 << 20, 0) == EINVAL
     assert lib.goom_probe_bandwidth(None, None, p, 1 << 20, 1) == EINVAL and "context" in err(lib)
+    assert lib.goom_probe_matrix_unit(None, None, 16, 0) == EINVAL
+    assert lib.goom_probe_matrix_unit(None, p, 0, 0) == EINVAL and "iters" in err(lib)
+    assert lib.goom_probe_matrix_unit(None, p, 16, 1) == EINVAL and "context" in err(lib)
     # context
     assert lib.goom_create(None, 0, None) == EINVAL
     ctx = C.c_void_p()

@@ -858,6 +858,12 @@ def test_streaming_probes(G, oracle):
     keep = b.clone()
     G.probe_bandwidth(a, b, 0)
     assert torch.equal(b, keep) and torch.equal(a, torch.arange(n, dtype=torch.float32, device="cuda"))
+    # the matrix-unit probe runs and leaves its sink alone
+    sink = torch.zeros(4, device="cuda")
+    G.probe_matrix_unit(sink, 8)
+    G.probe_matrix_unit(sink, 8, double=True)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(sink).item() == 0
 
 
 # ------------------------------------------------------------------ degenerate cases of the method
