@@ -321,7 +321,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
     constexpr int LDA = DP + Comp<R>::kPad;
     constexpr int NITEMS = DP * LPR;
     constexpr int Q = (NITEMS + NT - 1) / NT;  // items per thread
-    constexpr bool PREFETCH = Q <= 16;         // items of the next factor wait in registers during the product
+    constexpr bool PREFETCH = Q <= 16 && !(sizeof(R) == 8 && DP >= 128); // items of the next factor wait in registers during the product
     constexpr int QB = PREFETCH ? Q : 8;       // items per batch
     typedef typename Comp<R>::vec4 vec4;
 
