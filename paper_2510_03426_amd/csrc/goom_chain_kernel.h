@@ -204,10 +204,12 @@ template <> struct Comp<double> {
     // ... so contraction index 16 kt + 4 v + g is stored at position 16 kt + 4 g + v, which
     // keeps the four values a lane needs contiguous
     __device__ static int phys(int j) { return (j & ~15) | ((j & 3) << 2) | ((j >> 2) & 3); }
+    // (the multiple of pi goes through a 32-bit integer: one conversion instruction, where a 64-bit one is a
+    // dozen; phases beyond 2^31 pi carry no parity in a double product with 1 / pi anyway)
     __device__ static bool is_negative(double im)
     {
-        long long k = (long long)__builtin_rint(im * 0.318309886183790671538);
-        return (k & 1LL) != 0;
+        const int k = (int)__builtin_rint(im * 0.318309886183790671538);
+        return (k & 1) != 0;
     }
     __device__ static double apply_sign(double x, double im) { return is_negative(im) ? -x : x; }
     __device__ static double exponent_of(double x) { return x != 0.0 ? (double)frexp_exp(x) : -1022.0; }
