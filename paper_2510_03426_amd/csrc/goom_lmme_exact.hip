@@ -59,7 +59,7 @@ template <> struct Num<double> {
         return x > -1200.0 ? y : 0.0;
     }
     __device__ static double log2_(double x) { return ::log2(x); }
-    __device__ static int parity(double im) { return (int)((long long)__builtin_rint(im * 0.318309886183790671538) & 1LL); }
+    __device__ static int parity(double im) { return (int)__builtin_rint(im * 0.318309886183790671538) & 1; }
 };
 
 constexpr int kOut = 64;    // a workgroup owns a 64 x 64 block of outputs, a thread 4 x 4 of them
