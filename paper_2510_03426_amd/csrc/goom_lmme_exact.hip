@@ -16,9 +16,10 @@
 //
 // One workgroup handles a 64 x 64 block of outputs of one batch item, a thread 4 x 4 of them, so that
 // one pair of LDS reads serves sixteen terms; the rows of A and the columns of B are staged in LDS 32
-// inner indices at a time.  A block whose outputs are all certified returns after the first sweep;
-// one with few outputs to repair hands them to its waves one at a time; only a block with many
-// (float components on wide-range data) runs the second sweep over all sixteen positions per thread.
+// inner indices at a time.  The certificate only needs the row maxima of A' and the column maxima of B'
+// (one light pass over the operands): a block whose outputs are all certified returns after it; one
+// with few outputs to repair hands them to its waves one at a time; only a block with many (float
+// components on wide-range data) runs the two sweeps over all sixteen positions per thread.
 #include "goom_chain_kernel.h"
 
 namespace {
@@ -130,31 +131,56 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
         __syncthreads();
     };
 
-    // ---- first sweep: largest pairwise sum of every output, row maxima of A and column maxima of B
-    R mx[4][4], amax[4], bmax[4];
+    // ---- row maxima of A' and column maxima of B' over the whole inner index: all the certificate needs.
+    // Straight from memory: a wave takes sixteen rows of A' (its lanes along the row, then a reduction across
+    // the lanes) and a quarter of the inner indices of B' (its lanes along the 64 columns).
+    __shared__ R s_amax[kOut], s_bmax[kOut], s_part[kThreads / 64][kOut];
+    {
+        const int lane = tid & 63, wave = tid >> 6;
+        R v[16];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        amax[r] = bmax[r] = Num<R>::neg_inf();
+        for (int rr = 0; rr < 16; ++rr) v[rr] = Num<R>::neg_inf();
+        for (int j = lane; j < d; j += 64) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) mx[r][c] = Num<R>::neg_inf();
-    }
-    for (int j0 = 0; j0 < d; j0 += kJBlock) {
-        stage(j0);
-#pragma unroll 4
-        for (int j = 0; j < kJBlock; ++j) {
-            R x[4], y[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) x[r] = are[(4 * ty + r) * LDA + j];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) y[c] = bre[j * kOut + 4 * tx + c];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                amax[r] = Num<R>::max_(x[r], amax[r]);
-                bmax[r] = Num<R>::max_(y[r], bmax[r]);
-#pragma unroll
-                for (int c = 0; c < 4; ++c) mx[r][c] = Num<R>::max_(x[r] + y[c], mx[r][c]);
+            for (int rr = 0; rr < 16; ++rr) {
+                const int i = i0 + 16 * wave + rr;
+                if (i < n) v[rr] = Num<R>::max_(v[rr], Ab[((size_t)i * d + j) * 2]);
             }
         }
+#pragma unroll
+        for (int rr = 0; rr < 16; ++rr) {
+            R w = v[rr];
+#pragma unroll
+            for (int sft = 1; sft < 64; sft <<= 1) w = Num<R>::max_(w, (R)__shfl_xor(w, sft, 64));
+            if (lane == 0) s_amax[16 * wave + rr] = w;
+        }
+        R cmaxv = Num<R>::neg_inf();
+        const int k = k0 + lane;
+        if (k < m) {
+            R part[4] = {Num<R>::neg_inf(), Num<R>::neg_inf(), Num<R>::neg_inf(), Num<R>::neg_inf()};
+            int j = wave;
+            for (; j + 12 < d; j += 16) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) part[u] = Num<R>::max_(part[u], Bb[((size_t)(j + 4 * u) * m + k) * 2]);
+            }
+            for (; j < d; j += 4) part[0] = Num<R>::max_(part[0], Bb[((size_t)j * m + k) * 2]);
+            cmaxv = Num<R>::max_(Num<R>::max_(part[0], part[1]), Num<R>::max_(part[2], part[3]));
+        }
+        s_part[wave][lane] = cmaxv;
+        __syncthreads();
+        if (tid < kOut) {
+            R w = s_part[0][tid];
+#pragma unroll
+            for (int u = 1; u < kThreads / 64; ++u) w = Num<R>::max_(w, s_part[u][tid]);
+            s_bmax[tid] = w;
+        }
+        __syncthreads();
+    }
+    R amax[4], bmax[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        amax[r] = s_amax[4 * ty + r];
+        bmax[r] = s_bmax[4 * tx + r];
     }
     // ---- certificate: which outputs of the scaled product may have lost terms to underflow
     unsigned need = 0;
@@ -219,8 +245,29 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
         return;
     }
 
-    // ---- second sweep: signed sums of exponentials relative to the largest pairwise sum.  Every thread
-    // stages; a wave none of whose outputs needs repair skips the arithmetic.
+    // ---- many outputs to repair: first the largest pairwise sum of every output of the block ...
+    R mx[4][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) mx[r][c] = Num<R>::neg_inf();
+    for (int j0 = 0; j0 < d; j0 += kJBlock) {
+        stage(j0);
+#pragma unroll 4
+        for (int j = 0; j < kJBlock; ++j) {
+            R x[4], y[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) x[r] = are[(4 * ty + r) * LDA + j];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) y[c] = bre[j * kOut + 4 * tx + c];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) mx[r][c] = Num<R>::max_(x[r] + y[c], mx[r][c]);
+        }
+    }
+    // ---- ... then the signed sums of exponentials relative to it.  Every thread stages; a wave none of
+    // whose outputs needs repair skips the arithmetic.
     const bool wave_needs = __builtin_amdgcn_ballot_w64(need != 0) != 0;
     // which of the sixteen output positions any lane of this wave has to repair: when repairs are rare
     // (double components), most positions are skipped by the whole wave
