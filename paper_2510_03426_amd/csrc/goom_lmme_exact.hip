@@ -91,7 +91,16 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
     const int tid = threadIdx.x;
     const int ty = tid / 16, tx = tid % 16;
     const int blocks_k = (m + kOut - 1) / kOut, blocks_i = (n + kOut - 1) / kOut;
-    const long long bid = blockIdx.x;
+    // Workgroups go to the eight XCDs in turn, each with an L2 of its own: renumber them so that the blocks of
+    // one batch item (which share rows of A' and columns of B') run on the same XCD, one after the other.
+    long long bid = blockIdx.x;
+    {
+        const long long per_item = (long long)blocks_i * blocks_k, span = 8 * per_item;
+        if (bid < (long long)gridDim.x / span * span) {
+            const long long grp = bid / span, r = bid % span;
+            bid = (grp * 8 + r % 8) * per_item + r / 8;
+        }
+    }
     const long long b = bid / ((long long)blocks_i * blocks_k);
     const int rem = (int)(bid % ((long long)blocks_i * blocks_k));
     const int i0 = (rem / blocks_k) * kOut, k0 = (rem % blocks_k) * kOut;
