@@ -176,6 +176,13 @@ def test_long_scans_of_small_matrices(G, oracle, d, tmax):
     long_scan_case(G, oracle, 1 << 22, d, 512, 32768, tmax, 500, 1 << 19, 80 + d, 1.5e-3)
 
 
+@pytest.mark.parametrize("d,T", [(48, 1 << 19), (96, 1 << 17)])
+def test_long_scans_between_tiles(G, oracle, d, T):
+    # 48 x 48 and 96 x 96 matrices as the benchmark runs them (chunks of 512 steps; the hot kernel with the
+    # rows and columns beyond the matrix left out of the product)
+    long_scan_case(G, oracle, T, d, 512, 1200, T, 300, 1 << 14, 200 + d, 3e-3)
+
+
 def test_long_scan_128(G, oracle):
     # T = 2^18 chain of 128 x 128 matrices (256 chunks of 1024 steps, one workgroup per compute unit)
     long_scan_case(G, oracle, 1 << 18, 128, 1024, 2048, 1 << 18, 300, 1 << 14, 128, 2e-3)
