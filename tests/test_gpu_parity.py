@@ -170,7 +170,7 @@ def test_decode_accepts_any_phase_multiple(G, oracle):
 
 @pytest.mark.parametrize("shape", [(1, 8, 8, 8), (3, 16, 16, 16), (2, 5, 7, 3), (2, 64, 64, 64), (2, 128, 128, 128),
                                    (1, 33, 20, 1), (2, 1, 1, 1), (1, 100, 128, 60), (2, 3, 32, 64), (1, 31, 1, 128), (2, 1, 17, 128),
-                                   (1, 16, 4, 40)])
+                                   (1, 16, 4, 40), (2, 48, 48, 48), (1, 96, 96, 96), (3, 20, 20, 20), (1, 124, 124, 124)])
 def test_lmme_matches_oracle(G, oracle, shape):
     b, n, d, m = shape
     say(f"lmme batch={b} n={n} d={d} m={m}")
