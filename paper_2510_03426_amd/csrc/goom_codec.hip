@@ -78,12 +78,14 @@ __device__ inline double exp_of_f32(float xf)
     return __builtin_ldexp(p, (int)k);
 }
 
+// (straight-line: the series runs on every input, zeros, infinities and NaN included, and the special results
+// are selected afterwards; with the special cases as branches the four elements of a thread serialised)
 __device__ inline float enc_re_f32(float v, bool zero_floor)
 {
-    if (v == 0.0f) return zero_floor ? (float)kFloorF32 : -__builtin_huge_valf();
     const float av = __builtin_fabsf(v);
-    if (!(av < __builtin_huge_valf())) return av; // infinities and NaN pass through
-    return (float)ln_abs_f64((double)av);
+    float r = (float)ln_abs_f64((double)av);
+    r = av < __builtin_huge_valf() ? r : av; // infinities and NaN pass through
+    return v == 0.0f ? (zero_floor ? (float)kFloorF32 : -__builtin_huge_valf()) : r;
 }
 
 __global__ __launch_bounds__(256) void to_goom_f32_kernel(const float *__restrict__ x, float *__restrict__ y,
