@@ -275,7 +275,8 @@ template <> struct Comp<double> {
     }
     __device__ static double out_re(double x, double n, double e)
     {
-        return x != 0.0 ? __builtin_fma(n + e, kLn2, ln_abs(x)) : neg_inf();
+        const double l = __builtin_fma(n + e, kLn2, ln_abs(x)); // evaluated for zero as well, then discarded: no branch
+        return x != 0.0 ? l : neg_inf();
     }
 };
 

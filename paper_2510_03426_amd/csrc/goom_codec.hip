@@ -55,9 +55,9 @@ __device__ inline double ln_abs_f64(double x)
 // such x), e^r as its series to r^13 (|r| < 0.35: remainder below 1e-17), scaled by 2^k.
 __device__ inline double exp_of_f32(float xf)
 {
-    const double x = (double)xf;
-    if (!(x > -800.0)) return x == x ? 0.0 : x;              // -inf and everything that underflows even in double; NaN stays
-    if (!(x < 800.0)) return __builtin_huge_val();            // overflows float by far
+    // (straight-line: out-of-range arguments are clamped for the series and their results selected at the end)
+    const double x0 = (double)xf;
+    const double x = __builtin_fmin(__builtin_fmax(x0, -800.0), 800.0); // NaN -> -800 here, restored below
     const double k = __builtin_rint(x * 1.44269504088896340736);
     const double kLn2Hi = 0.693147180369123816490, kLn2Lo = 1.90821492927058770002e-10;
     const double r = __builtin_fma(-k, kLn2Lo, __builtin_fma(-k, kLn2Hi, x));
@@ -75,7 +75,10 @@ __device__ inline double exp_of_f32(float xf)
     p = __builtin_fma(p, r, 0.5);
     p = __builtin_fma(p, r, 1.0);
     p = __builtin_fma(p, r, 1.0);
-    return __builtin_ldexp(p, (int)k);
+    double y = __builtin_ldexp(p, (int)k);
+    y = x0 > -800.0 ? y : 0.0;                    // -inf and everything that underflows even in double
+    y = x0 < 800.0 ? y : __builtin_huge_val();    // overflows float by far
+    return x0 == x0 ? y : x0;                     // NaN stays
 }
 
 // (straight-line: the series runs on every input, zeros, infinities and NaN included, and the special results
