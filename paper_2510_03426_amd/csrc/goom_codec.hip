@@ -20,18 +20,12 @@ constexpr double kInvPi = 0.318309886183790671538;
 // s = (m - 1) / (m + 1), |s| < 0.1716, as its series to s^21 (remainder below 1e-17 relative; near x = 1
 // the result is the series alone, so it keeps its relative accuracy there).  About a third of the
 // instructions of the library routine, which made the float encoder compute bound.
-__device__ inline double ln_abs_f64(double x)
+// k ln 2 + 2 atanh(num / den), the common tail of the logarithms below: |num / den| < 0.1716
+__device__ inline double ln_from_ratio(double num, double den, double k)
 {
-    int k;
-    double m = __builtin_frexp(__builtin_fabs(x), &k); // [1/2, 1)
-    const bool low = m < 0.70710678118654752440;
-    m = low ? m + m : m;
-    k = low ? k - 1 : k;
-    const double den = m + 1.0;
     double r = (double)__builtin_amdgcn_rcpf((float)den);
     r = r * (2.0 - den * r);
     r = r * (2.0 - den * r);
-    const double num = m - 1.0;
     double s = num * r;
     s = __builtin_fma(__builtin_fma(-s, den, num), r, s); // s = num / den to rounding
     const double z = s * s;
@@ -48,15 +42,35 @@ __device__ inline double ln_abs_f64(double x)
     p = __builtin_fma(p, z * s, s); // s + s^3 (1/3 + ...)
     // k ln 2 with ln 2 in two parts: the high part has 32 significant bits, so k times it is exact
     const double kLn2Hi = 0.693147180369123816490, kLn2Lo = 1.90821492927058770002e-10;
-    return __builtin_fma((double)k, kLn2Hi, __builtin_fma((double)k, kLn2Lo, p + p));
+    return __builtin_fma(k, kLn2Hi, __builtin_fma(k, kLn2Lo, p + p));
 }
 
-// e^x in double for a float x: k = round(x / ln 2), r = x - k ln 2 with ln 2 in two parts (exact for
-// such x), e^r as its series to r^13 (|r| < 0.35: remainder below 1e-17), scaled by 2^k.
-__device__ inline double exp_of_f32(float xf)
+// x = m 2^k with m in [sqrt(1/2), sqrt(2)): the ratio (m - 1) / (m + 1) and k for the tail above
+__device__ inline void ln_reduce(double x, double &num, double &den, double &kd)
 {
-    // (straight-line: out-of-range arguments are clamped for the series and their results selected at the end)
-    const double x0 = (double)xf;
+    int k;
+    double m = __builtin_frexp(__builtin_fabs(x), &k); // [1/2, 1)
+    const bool low = m < 0.70710678118654752440;
+    m = low ? m + m : m;
+    k = low ? k - 1 : k;
+    num = m - 1.0;
+    den = m + 1.0;
+    kd = (double)k;
+}
+
+__device__ inline double ln_abs_f64(double x)
+{
+    double num, den, kd;
+    ln_reduce(x, num, den, kd);
+    return ln_from_ratio(num, den, kd);
+}
+
+// e^x in double: k = round(x / ln 2), r = x - k ln 2 with ln 2 in two parts (exact for a float x), e^r as
+// its series to r^13 (|r| < 0.35: remainder below 1e-17), scaled by 2^k.  Also returns, for k = 0, the
+// series of e^r - 1 with its relative accuracy (r times the series without its last step).
+// (straight-line: out-of-range arguments are clamped for the series and their results selected at the end)
+__device__ inline double exp_series(double x0, double *expm1_small = nullptr, bool *k_is_zero = nullptr)
+{
     const double x = __builtin_fmin(__builtin_fmax(x0, -800.0), 800.0); // NaN -> -800 here, restored below
     const double k = __builtin_rint(x * 1.44269504088896340736);
     const double kLn2Hi = 0.693147180369123816490, kLn2Lo = 1.90821492927058770002e-10;
@@ -74,12 +88,16 @@ __device__ inline double exp_of_f32(float xf)
     p = __builtin_fma(p, r, 1.0 / 6.0);
     p = __builtin_fma(p, r, 0.5);
     p = __builtin_fma(p, r, 1.0);
+    if (expm1_small) *expm1_small = p * r;
+    if (k_is_zero) *k_is_zero = k == 0.0;
     p = __builtin_fma(p, r, 1.0);
     double y = __builtin_ldexp(p, (int)k);
     y = x0 > -800.0 ? y : 0.0;                    // -inf and everything that underflows even in double
     y = x0 < 800.0 ? y : __builtin_huge_val();    // overflows float by far
     return x0 == x0 ? y : x0;                     // NaN stays
 }
+
+__device__ inline double exp_of_f32(float xf) { return exp_series((double)xf); }
 
 // (straight-line: the series runs on every input, zeros, infinities and NaN included, and the special results
 // are selected afterwards; with the special cases as branches the four elements of a thread serialised)
@@ -130,10 +148,12 @@ __global__ __launch_bounds__(256) void to_goom_f64_kernel(const double *__restri
     }
 }
 
+// (through a 32-bit integer: one conversion instruction where a 64-bit one is a dozen; a phase beyond
+// 2^31 pi carries no parity in a double product with 1 / pi anyway)
 __device__ inline bool odd_multiple_of_pi(double im)
 {
-    long long k = (long long)__builtin_rint(im * kInvPi);
-    return (k & 1LL) != 0;
+    const int k = (int)__builtin_rint(im * kInvPi);
+    return (k & 1) != 0;
 }
 
 __global__ __launch_bounds__(256) void from_goom_f32_kernel(const float *__restrict__ y, float *__restrict__ x, size_t n)
@@ -183,7 +203,10 @@ template <typename R, typename R2> __global__ __launch_bounds__(256) void scaled
             const int i = el + r * group;
             if (live && i < d) {
                 const R2 e = z[v * d + i];
-                double x = m > -__builtin_huge_val() ? exp((double)e.x - m + 2.0) : 0.0;
+                const double arg = (double)e.x - m + 2.0;
+                // float results: the short series (good to 1e-13 for such arguments); double results: the library's
+                double x = sizeof(R) == 4 ? exp_series(arg) : exp(arg);
+                x = m > -__builtin_huge_val() ? x : 0.0;
                 if (odd_multiple_of_pi((double)e.y)) x = -x;
                 out[v * d + i] = (R)x;
             }
@@ -195,6 +218,54 @@ template <typename R, typename R2> __global__ __launch_bounds__(256) void scaled
 // Signed log-add of two GOOM arrays: the GOOM of exp(x') + exp(y') (paper Section 2, Example 2; the
 // bias step of eq. 20).  In double, rounded once: with m the larger log-magnitude and delta the gap,
 // m + log1p(exp(-delta)) for equal signs, m + log(-expm1(-delta)) for opposite ones.
+// Float components: the same in straight-line code on the short series.  With a the larger log-magnitude,
+// delta = a - b >= 0 and e = exp(-delta): equal signs give a + ln(1 + e), where the ratio for the atanh series is
+// formed from e itself (e / (2 + e), or (e - 1) / (e + 3) plus ln 2 above sqrt(2) - 1), so a tiny e keeps its
+// relative accuracy; opposite signs give a + ln(1 - e), with 1 - e taken from the series of e^r - 1 when
+// delta < (ln 2) / 2, where the subtraction would cancel.
+__global__ __launch_bounds__(256) void log_add_exp_f32_kernel(const float2 *__restrict__ x, const float2 *__restrict__ y,
+                                                              float2 *__restrict__ out, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const double ninf = -__builtin_huge_val();
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const float2 p = x[i], q = y[i];
+        const bool sp = odd_multiple_of_pi((double)p.y), sq = odd_multiple_of_pi((double)q.y);
+        // the larger magnitude first; of two equal ones the non-negative
+        const bool swap = q.x > p.x || (q.x == p.x && !sq && sp);
+        const double a = swap ? (double)q.x : (double)p.x, b = swap ? (double)p.x : (double)q.x;
+        const bool sa = swap ? sq : sp, sb = swap ? sp : sq;
+        const bool same = sa == sb;
+        const double delta = b > ninf ? a - b : 800.0; // (a = b = -inf would give NaN: selected away below)
+        double em1;
+        bool k0;
+        const double e = exp_series(-delta, &em1, &k0); // in (0, 1]
+        // 1 - e without cancellation
+        const double u = k0 ? -em1 : 1.0 - e;
+        double num_d, den_d, k_d;
+        ln_reduce(u, num_d, den_d, k_d); // garbage for u = 0, selected away below
+        const bool big = e > 0.41421356237309504880;
+        const double num = same ? (big ? e - 1.0 : e) : num_d;
+        const double den = same ? (big ? e + 3.0 : e + 2.0) : den_d;
+        const double kd = same ? (big ? 1.0 : 0.0) : k_d;
+        double re = a + ln_from_ratio(num, den, kd);
+        bool neg = sa;
+        const bool cancel = !same && delta == 0.0;
+        re = cancel ? ninf : re;
+        neg = cancel ? false : neg;
+        re = b > ninf ? re : a;          // a zero second operand: the first one as it is
+        const bool zero = !(a > ninf);   // both zero (a is the larger)
+        re = zero ? ninf : re;
+        neg = zero ? false : neg;
+        re = a < __builtin_huge_val() ? re : a; // +inf stays
+        re = (a == a && b == b) ? re : a + b;   // NaN stays
+        float2 o;
+        o.x = (float)re;
+        o.y = neg ? kPiF : 0.0f;
+        out[i] = o;
+    }
+}
+
 template <typename R, typename R2> __global__ __launch_bounds__(256) void log_add_exp_kernel(const R2 *__restrict__ x, const R2 *__restrict__ y,
                                                                                              R2 *__restrict__ out, size_t n, R pi)
 {
@@ -284,8 +355,8 @@ int launch_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, s
     if (n == 0) return GOOM_OK;
     prof_begin(ctx, "log_add_exp");
     if (dtype == GOOM_C64)
-        hipLaunchKernelGGL((log_add_exp_kernel<float, float2>), dim3(grid_for(n)), dim3(256), 0, ctx->stream, static_cast<const float2 *>(x),
-                           static_cast<const float2 *>(y), static_cast<float2 *>(out), n, 3.14159274101257324219f);
+        hipLaunchKernelGGL(log_add_exp_f32_kernel, dim3(grid_for(n)), dim3(256), 0, ctx->stream, static_cast<const float2 *>(x),
+                           static_cast<const float2 *>(y), static_cast<float2 *>(out), n);
     else
         hipLaunchKernelGGL((log_add_exp_kernel<double, double2>), dim3(grid_for(n)), dim3(256), 0, ctx->stream, static_cast<const double2 *>(x),
                            static_cast<const double2 *>(y), static_cast<double2 *>(out), n, 3.14159265358979311600);
