@@ -193,16 +193,30 @@ template <typename R, typename R2> __global__ __launch_bounds__(256) void scaled
     for (size_t v0 = wave * per_wave; v0 < nvec; v0 += nwaves * per_wave) {
         const size_t v = v0 + sub;
         const bool live = v < nvec;
-        double m = -__builtin_huge_val();
-        for (int r = 0; r < reps; ++r) {
+        // (the maximum in the component type: exact, and for floats half the lane exchanges of a double)
+        R mr = sizeof(R) == 4 ? (R)-__builtin_huge_valf() : (R)-__builtin_huge_val();
+        R2 first;
+        first.x = mr;
+        first.y = (R)0;
+        if (live && el < d) first = z[v * d + el];
+        mr = first.x;
+        for (int r = 1; r < reps; ++r) {
             const int i = el + r * group;
-            if (live && i < d) m = fmax(m, (double)z[v * d + i].x);
+            if (live && i < d) {
+                const R t = z[v * d + i].x;
+                mr = t > mr ? t : mr;
+            }
         }
-        for (int sft = 1; sft < group; sft <<= 1) m = fmax(m, __shfl_xor(m, sft, 64));
+        for (int sft = 1; sft < group; sft <<= 1) {
+            const R o = __shfl_xor(mr, sft, 64);
+            mr = o > mr ? o : mr;
+        }
+        const double m = (double)mr;
         for (int r = 0; r < reps; ++r) {
             const int i = el + r * group;
             if (live && i < d) {
-                const R2 e = z[v * d + i];
+                // (floats keep the first element in its register; doubles are faster reading it again from cache)
+                const R2 e = (sizeof(R) == 4 && r == 0) ? first : z[v * d + i];
                 const double arg = (double)e.x - m + 2.0;
                 // float results: the short series (good to 1e-13 for such arguments); double results: the library's
                 double x = sizeof(R) == 4 ? exp_series(arg) : exp(arg);
