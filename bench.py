@@ -480,6 +480,13 @@ def recurrence(g, torch, dev, si):
     res["recurrence_time_invariant"] = {
         "ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1),
         "kernels_ms": kernel_times(g, lambda: g.affine_scan(a1, bz, out=h, time_invariant=True))}
+    # the elementwise ends of the recurrence as ops of their own, on the states just computed (nseq x T vectors of d):
+    # signed log-add (24 B per element) and scaled exponentiation (12 B per element)
+    o = torch.empty_like(h)
+    sec = timed(torch, lambda: g.log_add_exp(h, bz, out=o), 5)
+    res["log_add_exp_gbs"] = round(24.0 * h.numel() / sec / 1e9, 1)
+    sec = timed(torch, lambda: g.scaled_exp(h), 5)
+    res["scaled_exp_gbs"] = round(12.0 * h.numel() / sec / 1e9, 1)
     return res
 
 
