@@ -125,14 +125,19 @@ __global__ __launch_bounds__(256) void convert_right_kernel(const float2 *__rest
 }
 
 // ---- 3. C[b][M][N] = X[b][M][K] Y[b][N][K]^T, all row-major; M, N multiples of 128, K of 16.
-// grid (N / 128, M / 128, batch), 256 threads = 2 x 2 waves of 64 x 64.
+// grid (N / T, M / T, batch), 256 threads = 2 x 2 waves of (T / 2) x (T / 2), T = 32 WT: 128 x 128 tiles
+// (WT = 4) for throughput, 64 x 64 tiles (WT = 2) where a product has too few of the large ones to fill the
+// chip and its latency is what counts (the carry phase of a scan: one 256 x 256 product after the other).
 constexpr int BM = 128, BN = 128, BK = 16, LDK = BK + 4;
 
+template <int WT>
 __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const float *__restrict__ X, const float *__restrict__ Y, float *__restrict__ Cout, int M,
                                                           int N, int K, long long sx, long long sy, long long sc)
 {
-    __shared__ __align__(16) float xs[2][BM * LDK];
-    __shared__ __align__(16) float ys[2][BN * LDK];
+    constexpr int TM = 32 * WT;      // tile edge
+    constexpr int NL = TM * 4 / 256; // 16-byte pieces of a TM x 16 tile per thread
+    __shared__ __align__(16) float xs[2][TM * LDK];
+    __shared__ __align__(16) float ys[2][TM * LDK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, c = lane & 15;
     const int wm = wave >> 1, wn = wave & 1;
@@ -144,28 +149,30 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const float *__restrict
     if (nwg % 8 == 0) lin = (lin % 8) * (nwg / 8) + lin / 8;
     const unsigned bx = (unsigned)(lin % tiles_x), by = (unsigned)((lin / tiles_x) % tiles_y);
     const long long b = (long long)(lin / ((unsigned long long)tiles_x * tiles_y));
-    const float *Xb = X + b * sx + (size_t)by * BM * K;
-    const float *Yb = Y + b * sy + (size_t)bx * BN * K;
-    // global -> registers: the 128 x 16 tile is 512 pieces of four floats; a thread takes two
-    const int r0 = tid >> 2, r1 = r0 + 64, kq = (tid & 3) * 4;
-    f4 xr0, xr1, yr0, yr1;
+    const float *Xb = X + b * sx + (size_t)by * TM * K;
+    const float *Yb = Y + b * sy + (size_t)bx * TM * K;
+    // global -> registers: the TM x 16 tile is TM * 4 pieces of four floats; a thread takes NL of each operand
+    const int r0 = tid >> 2, kq = (tid & 3) * 4;
+    f4 xr[NL], yr[NL];
     auto load_tiles = [&](int k0) {
-        xr0 = *reinterpret_cast<const f4 *>(Xb + (size_t)r0 * K + k0 + kq);
-        xr1 = *reinterpret_cast<const f4 *>(Xb + (size_t)r1 * K + k0 + kq);
-        yr0 = *reinterpret_cast<const f4 *>(Yb + (size_t)r0 * K + k0 + kq);
-        yr1 = *reinterpret_cast<const f4 *>(Yb + (size_t)r1 * K + k0 + kq);
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            xr[u] = *reinterpret_cast<const f4 *>(Xb + (size_t)(r0 + 64 * u) * K + k0 + kq);
+            yr[u] = *reinterpret_cast<const f4 *>(Yb + (size_t)(r0 + 64 * u) * K + k0 + kq);
+        }
     };
     auto store_tiles = [&](int buf) {
-        *reinterpret_cast<f4 *>(&xs[buf][r0 * LDK + kq]) = xr0;
-        *reinterpret_cast<f4 *>(&xs[buf][r1 * LDK + kq]) = xr1;
-        *reinterpret_cast<f4 *>(&ys[buf][r0 * LDK + kq]) = yr0;
-        *reinterpret_cast<f4 *>(&ys[buf][r1 * LDK + kq]) = yr1;
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            *reinterpret_cast<f4 *>(&xs[buf][(r0 + 64 * u) * LDK + kq]) = xr[u];
+            *reinterpret_cast<f4 *>(&ys[buf][(r0 + 64 * u) * LDK + kq]) = yr[u];
+        }
     };
-    f4 acc[4][4];
+    f4 acc[WT][WT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WT; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = f4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < WT; ++j) acc[i][j] = f4{0.f, 0.f, 0.f, 0.f};
     const int nk = K / BK;
     load_tiles(0);
     store_tiles(0);
@@ -173,29 +180,39 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const float *__restrict
     int buf = 0;
     for (int kt = 0; kt < nk; ++kt) {
         if (kt + 1 < nk) load_tiles((kt + 1) * BK);
-        f4 av[4], bv[4];
+        f4 av[WT], bv[WT];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            av[i] = *reinterpret_cast<const f4 *>(&xs[buf][(wm * 64 + 16 * i + c) * LDK + 4 * g]);
-            bv[i] = *reinterpret_cast<const f4 *>(&ys[buf][(wn * 64 + 16 * i + c) * LDK + 4 * g]);
+        for (int i = 0; i < WT; ++i) {
+            av[i] = *reinterpret_cast<const f4 *>(&xs[buf][(wm * 16 * WT + 16 * i + c) * LDK + 4 * g]);
+            bv[i] = *reinterpret_cast<const f4 *>(&ys[buf][(wn * 16 * WT + 16 * i + c) * LDK + 4 * g]);
         }
 #pragma unroll
         for (int v = 0; v < 4; ++v)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < WT; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = CF::mfma(av[i][v], bv[j][v], acc[i][j]);
+                for (int j = 0; j < WT; ++j) acc[i][j] = CF::mfma(av[i][v], bv[j][v], acc[i][j]);
         if (kt + 1 < nk) store_tiles(buf ^ 1);
         __syncthreads();
         buf ^= 1;
     }
-    float *Cb = Cout + b * sc + ((size_t)by * BM + wm * 64) * N + (size_t)bx * BN + wn * 64;
+    float *Cb = Cout + b * sc + ((size_t)by * TM + wm * 16 * WT) * N + (size_t)bx * TM + wn * 16 * WT;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WT; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < WT; ++j)
 #pragma unroll
             for (int v = 0; v < 4; ++v) Cb[(size_t)(16 * i + 4 * g + v) * N + 16 * j + c] = acc[i][j][v];
+}
+
+// gx, gy: the grid in 128 x 128 tiles
+inline void launch_gemm_nt(hipStream_t st, const float *X, const float *Y, float *C, unsigned gx, unsigned gy, unsigned gz, int M, int N, int K,
+                           long long sx, long long sy, long long sc)
+{
+    if ((unsigned long long)gx * gy * gz < 128)
+        hipLaunchKernelGGL(gemm_nt_kernel<2>, dim3(2 * gx, 2 * gy, gz), dim3(256), 0, st, X, Y, C, M, N, K, sx, sy, sc);
+    else
+        hipLaunchKernelGGL(gemm_nt_kernel<4>, dim3(gx, gy, gz), dim3(256), 0, st, X, Y, C, M, N, K, sx, sy, sc);
 }
 
 // ---- 4. C'[b][i][k] = GOOM of Ct[b][k][i] 2^(row_shift_i + col_shift_k).
@@ -266,8 +283,7 @@ int launch_lmme_large(goom_ctx *ctx, const void *A, const void *B, void *C, long
     prof_end(ctx);
     if (int s = check_hip(ctx, hipGetLastError(), "launch LMME operand kernels")) return s;
     prof_begin(ctx, "lmme_large_gemm");
-    hipLaunchKernelGGL(gemm_nt_kernel, dim3(Np / BN, Mp / BM, nb), dim3(256), 0, ctx->stream, Y, X, Ct, Mp, Np, Kp, (long long)Mp * Kp,
-                       (long long)Np * Kp, (long long)Mp * Np);
+    launch_gemm_nt(ctx->stream, Y, X, Ct, Np / BN, Mp / BM, nb, Mp, Np, Kp, (long long)Mp * Kp, (long long)Np * Kp, (long long)Mp * Np);
     prof_end(ctx);
     if (int s = check_hip(ctx, hipGetLastError(), "launch gemm_nt_kernel")) return s;
     prof_begin(ctx, "lmme_large_log_store");
@@ -291,7 +307,7 @@ struct OpsF32 {
     static void gemm(hipStream_t st, const float *X, const float *Y, float *C, unsigned gx, unsigned gy, unsigned gz, int M, int N, int K,
                      long long sx, long long sy, long long sc)
     {
-        hipLaunchKernelGGL(gemm_nt_kernel, dim3(gx, gy, gz), dim3(256), 0, st, X, Y, C, M, N, K, sx, sy, sc);
+        launch_gemm_nt(st, X, Y, C, gx, gy, gz, M, N, K, sx, sy, sc);
     }
     static void init_state(hipStream_t st, const void *init, double *ey, float *yt, int d, int m, int mp, int dp, unsigned batch)
     {
