@@ -127,12 +127,16 @@ __global__ __launch_bounds__(256) void convert_right_f64_kernel(const double2 *_
 // lanes read at once then start in sixteen different groups of four banks.
 constexpr int BM = 128, BN = 128, BK = 16, LDK = BK + 2;
 
+// WT = 4: 128 x 128 tiles; WT = 2: 64 x 64 tiles, for products with too few of the large ones to fill the chip
+template <int WT>
 __global__ __launch_bounds__(256, 2) void gemm_nt_f64_kernel(const double *__restrict__ X, const double *__restrict__ Y, double *__restrict__ Cout,
                                                               int M, int N, int K, long long sx, long long sy, long long sc)
 {
+    constexpr int TM = 32 * WT;      // tile edge
+    constexpr int NL = TM * 4 / 256; // 32-byte pieces of a TM x 16 tile per thread
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    double *xs = reinterpret_cast<double *>(smem_raw);          // [2][BM * LDK]
-    double *ys = xs + 2 * BM * LDK;                             // [2][BN * LDK]
+    double *xs = reinterpret_cast<double *>(smem_raw);          // [2][TM * LDK]
+    double *ys = xs + 2 * TM * LDK;                             // [2][TM * LDK]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, c = lane & 15;
     const int wm = wave >> 1, wn = wave & 1;
@@ -144,30 +148,34 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_f64_kernel(const double *__res
     if (nwg % 8 == 0) lin = (lin % 8) * (nwg / 8) + lin / 8;
     const unsigned bx = (unsigned)(lin % tiles_x), by = (unsigned)((lin / tiles_x) % tiles_y);
     const long long b = (long long)(lin / ((unsigned long long)tiles_x * tiles_y));
-    const double *Xb = X + b * sx + (size_t)by * BM * K;
-    const double *Yb = Y + b * sy + (size_t)bx * BN * K;
-    // global -> registers: a 128 x 16 tile is 512 pieces of four doubles; a thread takes two of each operand
-    const int r0 = tid >> 2, r1 = r0 + 64, kq = (tid & 3) * 4;
-    d2 xr[4], yr[4];
+    const double *Xb = X + b * sx + (size_t)by * TM * K;
+    const double *Yb = Y + b * sy + (size_t)bx * TM * K;
+    // global -> registers: a TM x 16 tile is TM * 4 pieces of four doubles; a thread takes NL of each operand
+    const int r0 = tid >> 2, kq = (tid & 3) * 4;
+    d2 xr[2 * NL], yr[2 * NL];
     auto load_tiles = [&](int k0) {
-        const d2 *p;
-        p = reinterpret_cast<const d2 *>(Xb + (size_t)r0 * K + k0 + kq); xr[0] = p[0]; xr[1] = p[1];
-        p = reinterpret_cast<const d2 *>(Xb + (size_t)r1 * K + k0 + kq); xr[2] = p[0]; xr[3] = p[1];
-        p = reinterpret_cast<const d2 *>(Yb + (size_t)r0 * K + k0 + kq); yr[0] = p[0]; yr[1] = p[1];
-        p = reinterpret_cast<const d2 *>(Yb + (size_t)r1 * K + k0 + kq); yr[2] = p[0]; yr[3] = p[1];
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            const d2 *p = reinterpret_cast<const d2 *>(Xb + (size_t)(r0 + 64 * u) * K + k0 + kq);
+            xr[2 * u] = p[0]; xr[2 * u + 1] = p[1];
+            p = reinterpret_cast<const d2 *>(Yb + (size_t)(r0 + 64 * u) * K + k0 + kq);
+            yr[2 * u] = p[0]; yr[2 * u + 1] = p[1];
+        }
     };
     auto store_tiles = [&](int buf) {
-        d2 *q;
-        q = reinterpret_cast<d2 *>(&xs[buf * BM * LDK + r0 * LDK + kq]); q[0] = xr[0]; q[1] = xr[1];
-        q = reinterpret_cast<d2 *>(&xs[buf * BM * LDK + r1 * LDK + kq]); q[0] = xr[2]; q[1] = xr[3];
-        q = reinterpret_cast<d2 *>(&ys[buf * BN * LDK + r0 * LDK + kq]); q[0] = yr[0]; q[1] = yr[1];
-        q = reinterpret_cast<d2 *>(&ys[buf * BN * LDK + r1 * LDK + kq]); q[0] = yr[2]; q[1] = yr[3];
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            d2 *q = reinterpret_cast<d2 *>(&xs[buf * TM * LDK + (r0 + 64 * u) * LDK + kq]);
+            q[0] = xr[2 * u]; q[1] = xr[2 * u + 1];
+            q = reinterpret_cast<d2 *>(&ys[buf * TM * LDK + (r0 + 64 * u) * LDK + kq]);
+            q[0] = yr[2 * u]; q[1] = yr[2 * u + 1];
+        }
     };
-    d4 acc[4][4];
+    d4 acc[WT][WT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WT; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = d4{0.0, 0.0, 0.0, 0.0};
+        for (int j = 0; j < WT; ++j) acc[i][j] = d4{0.0, 0.0, 0.0, 0.0};
     const int nk = K / BK;
     load_tiles(0);
     store_tiles(0);
@@ -175,34 +183,52 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_f64_kernel(const double *__res
     int buf = 0;
     for (int kt = 0; kt < nk; ++kt) {
         if (kt + 1 < nk) load_tiles((kt + 1) * BK);
-        const double *xb = xs + buf * BM * LDK, *yb = ys + buf * BN * LDK;
+        const double *xb = xs + buf * TM * LDK, *yb = ys + buf * TM * LDK;
 #pragma unroll
         for (int h = 0; h < 2; ++h) { // K = 4 g + 2 h, 4 g + 2 h + 1
-            d2 av[4], bv[4];
+            d2 av[WT], bv[WT];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                av[i] = *reinterpret_cast<const d2 *>(&xb[(wm * 64 + 16 * i + c) * LDK + 4 * g + 2 * h]);
-                bv[i] = *reinterpret_cast<const d2 *>(&yb[(wn * 64 + 16 * i + c) * LDK + 4 * g + 2 * h]);
+            for (int i = 0; i < WT; ++i) {
+                av[i] = *reinterpret_cast<const d2 *>(&xb[(wm * 16 * WT + 16 * i + c) * LDK + 4 * g + 2 * h]);
+                bv[i] = *reinterpret_cast<const d2 *>(&yb[(wn * 16 * WT + 16 * i + c) * LDK + 4 * g + 2 * h]);
             }
 #pragma unroll
             for (int v = 0; v < 2; ++v)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < WT; ++i)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[i][j] = CD::mfma(av[i][v], bv[j][v], acc[i][j]);
+                    for (int j = 0; j < WT; ++j) acc[i][j] = CD::mfma(av[i][v], bv[j][v], acc[i][j]);
         }
         if (kt + 1 < nk) store_tiles(buf ^ 1);
         __syncthreads();
         buf ^= 1;
     }
     // register v of lane group g holds row 4 v + g of a 16 x 16 tile
-    double *Cb = Cout + b * sc + ((size_t)by * BM + wm * 64) * N + (size_t)bx * BN + wn * 64;
+    double *Cb = Cout + b * sc + ((size_t)by * TM + wm * 16 * WT) * N + (size_t)bx * TM + wn * 16 * WT;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WT; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < WT; ++j)
 #pragma unroll
             for (int v = 0; v < 4; ++v) Cb[(size_t)(16 * i + CD::row_of(g, v)) * N + 16 * j + c] = acc[i][j][v];
+}
+
+constexpr size_t kGemmLds = (size_t)2 * (BM + BN) * LDK * sizeof(double); // of the 128 x 128 variant
+
+inline int prepare_gemm_f64(goom_ctx *ctx)
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_nt_f64_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLds);
+    return e == hipSuccess ? GOOM_OK : goom::check_hip(ctx, e, "hipFuncSetAttribute(gemm_nt_f64_kernel)");
+}
+
+// gx, gy: the grid in 128 x 128 tiles
+inline void launch_gemm_nt_f64(hipStream_t st, const double *X, const double *Y, double *C, unsigned gx, unsigned gy, unsigned gz, int M, int N,
+                               int K, long long sx, long long sy, long long sc)
+{
+    if ((unsigned long long)gx * gy * gz < 128)
+        hipLaunchKernelGGL(gemm_nt_f64_kernel<2>, dim3(2 * gx, 2 * gy, gz), dim3(256), kGemmLds / 2, st, X, Y, C, M, N, K, sx, sy, sc);
+    else
+        hipLaunchKernelGGL(gemm_nt_f64_kernel<4>, dim3(gx, gy, gz), dim3(256), kGemmLds, st, X, Y, C, M, N, K, sx, sy, sc);
 }
 
 // ---- 4. C'[b][i][k] = GOOM of Ct[b][k][i] 2^(row_shift_i + col_shift_k).
@@ -263,9 +289,7 @@ int launch_lmme_large_f64(goom_ctx *ctx, const void *A, const void *B, void *C, 
     w += align_up((size_t)batch * Mp * 8, 256);
     double *Ct = reinterpret_cast<double *>(w);
     const unsigned nb = (unsigned)batch;
-    const size_t lds = (size_t)2 * (BM + BN) * LDK * sizeof(double);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_nt_f64_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return check_hip(ctx, e, "hipFuncSetAttribute(gemm_nt_f64_kernel)");
+    if (int e = prepare_gemm_f64(ctx)) return e;
     prof_begin(ctx, "lmme_large_scale_operands");
     hipLaunchKernelGGL(convert_left_f64_kernel, dim3(Np, nb), dim3(256), 0, ctx->stream, static_cast<const double2 *>(A), X, rs, n, d, Np, Kp);
     hipLaunchKernelGGL(column_shift_f64_kernel, dim3(Mp / 64, nb), dim3(256), 0, ctx->stream, static_cast<const double2 *>(B), cs, d, m, Mp);
@@ -274,8 +298,7 @@ int launch_lmme_large_f64(goom_ctx *ctx, const void *A, const void *B, void *C, 
     prof_end(ctx);
     if (int s = check_hip(ctx, hipGetLastError(), "launch LMME operand kernels")) return s;
     prof_begin(ctx, "lmme_large_gemm");
-    hipLaunchKernelGGL(gemm_nt_f64_kernel, dim3(Np / BN, Mp / BM, nb), dim3(256), lds, ctx->stream, Y, X, Ct, Mp, Np, Kp, (long long)Mp * Kp,
-                       (long long)Np * Kp, (long long)Mp * Np);
+    launch_gemm_nt_f64(ctx->stream, Y, X, Ct, Np / BN, Mp / BM, nb, Mp, Np, Kp, (long long)Mp * Kp, (long long)Np * Kp, (long long)Mp * Np);
     prof_end(ctx);
     if (int s = check_hip(ctx, hipGetLastError(), "launch gemm_nt_f64_kernel")) return s;
     prof_begin(ctx, "lmme_large_log_store");
@@ -292,19 +315,13 @@ int launch_lmme_large_f64(goom_ctx *ctx, const void *A, const void *B, void *C, 
 // ------------------------------------------------------------------------------------------------
 namespace {
 
-constexpr size_t kGemmLds = (size_t)2 * (BM + BN) * LDK * sizeof(double);
-
 struct OpsF64 {
     static constexpr bool kResident = false;
-    static int prepare(goom_ctx *ctx)
-    {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_nt_f64_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLds);
-        return e == hipSuccess ? GOOM_OK : goom::check_hip(ctx, e, "hipFuncSetAttribute(gemm_nt_f64_kernel)");
-    }
+    static int prepare(goom_ctx *ctx) { return prepare_gemm_f64(ctx); }
     static void gemm(hipStream_t st, const double *X, const double *Y, double *C, unsigned gx, unsigned gy, unsigned gz, int M, int N, int K,
                      long long sx, long long sy, long long sc)
     {
-        hipLaunchKernelGGL(gemm_nt_f64_kernel, dim3(gx, gy, gz), dim3(256), kGemmLds, st, X, Y, C, M, N, K, sx, sy, sc);
+        launch_gemm_nt_f64(st, X, Y, C, gx, gy, gz, M, N, K, sx, sy, sc);
     }
     static void init_state(hipStream_t st, const void *init, double *ey, double *yt, int d, int m, int mp, int dp, unsigned batch)
     {
