@@ -130,16 +130,25 @@ __global__ __launch_bounds__(256) void convert_right_kernel(const float2 *__rest
 // chip and its latency is what counts (the carry phase of a scan: one 256 x 256 product after the other).
 constexpr int BM = 128, BN = 128, BK = 16, LDK = BK + 4;
 
+// The matrix instruction is the 32 x 32 x 2 form: twice the work per operand fetch of the 16 x 16 x 4 form, which
+// matters when several waves of a SIMD take turns (measured with instruction-only kernels: 138 against 104
+// TFLOP/s at two waves per SIMD).  Lane l supplies row (or column) l % 32 and one of two K values, l / 32; of
+// the sixteen K values of a step, instruction (t, v) contracts 8 t + v and 8 t + 4 + v, so that a lane's four
+// values per t are adjacent in LDS.  Register r of the result holds row 8 (r / 4) + 4 (l / 32) + r % 4 of
+// column l % 32.
+typedef float f16v __attribute__((ext_vector_type(16)));
+
 template <int WT>
 __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const float *__restrict__ X, const float *__restrict__ Y, float *__restrict__ Cout, int M,
                                                           int N, int K, long long sx, long long sy, long long sc)
 {
     constexpr int TM = 32 * WT;      // tile edge
     constexpr int NL = TM * 4 / 256; // 16-byte pieces of a TM x 16 tile per thread
+    constexpr int WB = WT / 2;       // 32 x 32 blocks per wave and dimension
     __shared__ __align__(16) float xs[2][TM * LDK];
     __shared__ __align__(16) float ys[2][TM * LDK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int g = lane >> 4, c = lane & 15;
+    const int h = lane >> 5, c = lane & 31;
     const int wm = wave >> 1, wn = wave & 1;
     // Workgroups are handed to the eight XCDs in turn, each with its own L2: renumber them so that one
     // XCD works on a contiguous range of tiles, whose operand panels it then shares in its L2.
@@ -168,11 +177,13 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const float *__restrict
             *reinterpret_cast<f4 *>(&ys[buf][(r0 + 64 * u) * LDK + kq]) = yr[u];
         }
     };
-    f4 acc[WT][WT];
+    f16v acc[WB][WB];
 #pragma unroll
-    for (int i = 0; i < WT; ++i)
+    for (int i = 0; i < WB; ++i)
 #pragma unroll
-        for (int j = 0; j < WT; ++j) acc[i][j] = f4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < WB; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     const int nk = K / BK;
     load_tiles(0);
     store_tiles(0);
@@ -180,29 +191,32 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const float *__restrict
     int buf = 0;
     for (int kt = 0; kt < nk; ++kt) {
         if (kt + 1 < nk) load_tiles((kt + 1) * BK);
-        f4 av[WT], bv[WT];
 #pragma unroll
-        for (int i = 0; i < WT; ++i) {
-            av[i] = *reinterpret_cast<const f4 *>(&xs[buf][(wm * 16 * WT + 16 * i + c) * LDK + 4 * g]);
-            bv[i] = *reinterpret_cast<const f4 *>(&ys[buf][(wn * 16 * WT + 16 * i + c) * LDK + 4 * g]);
+        for (int t = 0; t < 2; ++t) {
+            f4 av[WB], bv[WB];
+#pragma unroll
+            for (int i = 0; i < WB; ++i) {
+                av[i] = *reinterpret_cast<const f4 *>(&xs[buf][(wm * 16 * WT + 32 * i + c) * LDK + 8 * t + 4 * h]);
+                bv[i] = *reinterpret_cast<const f4 *>(&ys[buf][(wn * 16 * WT + 32 * i + c) * LDK + 8 * t + 4 * h]);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int i = 0; i < WB; ++i)
+#pragma unroll
+                    for (int j = 0; j < WB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][v], bv[j][v], acc[i][j], 0, 0, 0);
         }
-#pragma unroll
-        for (int v = 0; v < 4; ++v)
-#pragma unroll
-            for (int i = 0; i < WT; ++i)
-#pragma unroll
-                for (int j = 0; j < WT; ++j) acc[i][j] = CF::mfma(av[i][v], bv[j][v], acc[i][j]);
         if (kt + 1 < nk) store_tiles(buf ^ 1);
         __syncthreads();
         buf ^= 1;
     }
     float *Cb = Cout + b * sc + ((size_t)by * TM + wm * 16 * WT) * N + (size_t)bx * TM + wn * 16 * WT;
 #pragma unroll
-    for (int i = 0; i < WT; ++i)
+    for (int i = 0; i < WB; ++i)
 #pragma unroll
-        for (int j = 0; j < WT; ++j)
+        for (int j = 0; j < WB; ++j)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) Cb[(size_t)(16 * i + 4 * g + v) * N + 16 * j + c] = acc[i][j][v];
+            for (int r = 0; r < 16; ++r) Cb[(size_t)(32 * i + 8 * (r / 4) + 4 * h + r % 4) * N + 32 * j + c] = acc[i][j][r];
 }
 
 // gx, gy: the grid in 128 x 128 tiles
