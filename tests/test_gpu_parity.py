@@ -845,6 +845,34 @@ def test_caller_stream_and_profile_records(G, oracle):
     assert any("phase1" in l for l in labels) and any("phase3" in l for l in labels) and all(ms >= 0 for _, ms in recs)
 
 
+def test_scan_replays_from_a_captured_graph(G, oracle):
+    # the library allocates nothing, never synchronises and clears nothing with memsets, so a call can be recorded
+    # into a HIP graph: three replays on fresh inputs, eager work and synchronisations in between, each against
+    # the eager result on the same input
+    import torch
+    from paper_2510_03426_amd import Goom
+    T, d = 700, 64
+    zs = [dev(oracle.to_goom(si.normal_chain(si.BASE_SEED + 120 + i, T, d))) for i in range(3)]
+    z = torch.empty_like(zs[0])
+    out = torch.empty_like(z)
+    g2 = Goom(0)
+    z.copy_(zs[0])
+    g2.scan(z, chunk_len=50, out=out)  # sizes the cached workspace before anything is captured
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        g2.set_stream(torch.cuda.current_stream())
+        g2.scan(z, chunk_len=50, out=out)
+    g2.set_stream(torch.cuda.default_stream())
+    for i in (1, 2, 0):
+        want = host(G.scan(zs[i], chunk_len=50))
+        z.copy_(zs[i])
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        assert np.array_equal(host(out).view(np.uint32), want.view(np.uint32)), f"replay on input {i} differs from the eager scan"
+
+
 def test_streaming_probes(G, oracle):
     # the measurement aid: copy copies, fill fills, read leaves the data alone (ragged size, not a multiple of the grid)
     import torch
