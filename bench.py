@@ -33,7 +33,7 @@ def main():
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs")
     ap.add_argument("--no-extras", action="store_true", help="time the headline scan only")
-    ap.add_argument("--only", choices=["tiny", "between", "scan128", "lmme", "lyapunov", "recurrence", "large"], default=None,
+    ap.add_argument("--only", choices=["tiny", "between", "scan128", "complex128", "lmme", "lyapunov", "recurrence", "large"], default=None,
                     help="time just one of the other workloads (for profiler runs) and print its figures")
     ap.add_argument("--basic-extras", action="store_true",
                     help="besides the scan, time only a plain device copy of the same size (for counter runs)")
@@ -266,6 +266,8 @@ def other_workloads(g, torch, dev, only=None):
         res.update(scans_between_tiles(g, torch, dev, si))
     if want("scan128"):
         res.update(scan128(g, torch, dev, si))
+    if want("complex128"):
+        res.update(scans_complex128(g, torch, dev, si))
     if want("lmme"):
         res.update(batched_lmme(g, torch, dev, si))
     if want("lyapunov"):
@@ -314,6 +316,25 @@ def scans_between_tiles(g, torch, dev, si):
                                   "lmme_tflops_executed": round(fl / sec / 1e12, 2),
                                   "kernels_ms": kernel_times(g, lambda: g.scan(z, out=out))}
         del z, out
+    return res
+
+
+def scans_complex128(g, torch, dev, si):
+    # chains of complex128 GOOMs (double components, fp64 matrix instruction): 8.6 GB of matrices each
+    res = {}
+    for d, T in ((32, 1 << 19), (64, 1 << 18), (128, 1 << 16)):
+        z = g.to_goom(torch.randn((T, d, d), device=dev, dtype=torch.float64, generator=si.device_generator(251003426 * 10 + 100 + d, dev)))
+        out = torch.empty_like(z)
+        sec = timed(torch, lambda: g.scan(z, out=out), 3)
+        byts = 3 * z.numel() * 16  # read, read, write
+        fl = 2.0 * d ** 3 * 2 * T
+        res[f"scan_T{T}_d{d}_complex128"] = {"ms": round(sec * 1e3, 3), "products_per_s": round(T / sec, 1),
+                                             "hbm_gbs_algorithmic": round(byts / sec / 1e9, 1),
+                                             "lmme_tflops_executed": round(fl / sec / 1e12, 2),
+                                             "pct_of_fp64_mfma_peak": round(100 * fl / sec / 1e12 / MFMA_F64_PEAK_TFLOPS, 2),
+                                             "kernels_ms": kernel_times(g, lambda: g.scan(z, out=out))}
+        del z, out
+        torch.cuda.empty_cache()
     return res
 
 
