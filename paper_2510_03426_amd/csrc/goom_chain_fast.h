@@ -1,5 +1,6 @@
-// Hot variant of the chain kernel: float components, left factors given as GOOMs that
-// fill the padded tile exactly (d = 16, 32, 64 or 128), state of 16 * NW columns.
+// Hot variant of the chain kernel: float components, left factors given as GOOMs (or as real
+// matrices) that fill the padded tile exactly (d = 16, 32, 64 or 128), state of 16 * NW columns;
+// also, with the padding left out of the product, square sizes in between that are multiples of four.
 // This is the kernel the long scans spend their time in (phase 1 and phase 3 of the
 // three-phase scan; paper Section 4.1), and LMME on such shapes (Section 3.2).
 // With BIAS one more wave carries column d of the augmented state [A* | b*] of a linear
