@@ -114,13 +114,14 @@ def test_config2_long_chain_scan_full_size(G, oracle):
     del z, out
 
 
-def long_scan_case(G, oracle, T, d, L, keep, tmax, nbound, blk, seed, rate_tol):
+def long_scan_case(G, oracle, T, d, L, keep, tmax, nbound, blk, seed, rate_tol, real=False):
     """A scan with default options at a benchmark size: the leading `keep` steps against the oracle, the
     one-step recurrence at up to `nbound` chunk boundaries (chunks of L steps) and 100 interior steps below
     tmax, the reduction against the last prefix, the growth rate against its closed form."""
     import torch
     device = torch.device("cuda", 0)
-    z = torch.empty((T, d, d), dtype=torch.complex64, device=device)
+    # real=True: the scan is fed the real matrices themselves (goom_scan_real), not their encodings
+    z = torch.empty((T, d, d), dtype=torch.float32 if real else torch.complex64, device=device)
     rng = np.random.default_rng(seed)
     bounds = list(range(L, tmax, L))
     if len(bounds) > nbound:
@@ -130,17 +131,23 @@ def long_scan_case(G, oracle, T, d, L, keep, tmax, nbound, blk, seed, rate_tol):
     x_head = None
     say(f"long scan: T={T} d={d} ({len(sampled)} steps checked by the recurrence)")
     for t0, x in si.device_normal_blocks(si.BASE_SEED * 10 + seed, T, (d, d), device, blk):
-        G.to_goom(x, out=z[t0:t0 + x.shape[0]])
+        if real:
+            z[t0:t0 + x.shape[0]].copy_(x)
+        else:
+            G.to_goom(x, out=z[t0:t0 + x.shape[0]])
         if t0 == 0:
             x_head = x[:keep].cpu().numpy()
         for t in sampled:
             if t0 <= t < t0 + x.shape[0]:
                 x_keep[t] = x[t - t0].cpu().numpy()
         del x
-    out = G.scan(z)
+    out = G.scan_real(z) if real else G.scan(z)
     torch.cuda.synchronize()
-    zs = host(z[:keep])
-    assert np.array_equal(zs.view(np.uint32), oracle.to_goom(x_head).view(np.uint32))
+    if real:
+        zs = oracle.to_goom(x_head)
+    else:
+        zs = host(z[:keep])
+        assert np.array_equal(zs.view(np.uint32), oracle.to_goom(x_head).view(np.uint32))
     sample = sorted(t for t in ({0, 1, 2, 3, L - 1, L, L + 1, 2 * L - 1, 2 * L, 3 * L, keep - 1} | (set(range(keep // 7, keep, keep // 9)) if keep >= 9 else set())) if t < keep)
     fn = lambda mats: oracle.ScanStream(d, scaled=True).advance(mats, sample_t=sample, return_kappa=True)
     re, sg, kap, well = with_sensitivity(fn, [zs], np.float32, nprobe=1)
@@ -154,7 +161,7 @@ def long_scan_case(G, oracle, T, d, L, keep, tmax, nbound, blk, seed, rate_tol):
         bad_signs += signs
     say(f"  one-step recurrence at {len(sampled)} steps: worst defect {worst:.3f}, {bad_signs} sign mismatches")
     assert worst < 0.75 and bad_signs == 0
-    fin = host(G.reduce(z))
+    fin = host(G.scan_real(z, final_only=True) if real else G.reduce(z))
     last = host(out[T - 1])
     dre = np.abs(fin.real.astype(np.float64) - last.real.astype(np.float64))
     well_last = dre <= tolerance(last.real.astype(np.float64), np.float32)
@@ -166,6 +173,13 @@ def long_scan_case(G, oracle, T, d, L, keep, tmax, nbound, blk, seed, rate_tol):
     say(f"  log-magnitude of the last prefix: {last.real.max():.1f}; growth per step {rate:.5f} (closed form {lam:.5f})")
     assert abs(rate - lam) < rate_tol
     del z, out
+
+
+def test_config2_scan_of_real_matrices_full_size(G, oracle):
+    # the headline chain (T = 2^20 of 64 x 64) fed as real matrices, in the launch configuration bench.py times
+    # (1024 chunks of 1024 steps); the recurrence is checked below 2^18 (further on a stored log-magnitude is
+    # rounded too coarsely for the check to say much)
+    long_scan_case(G, oracle, 1 << 20, 64, 1024, 2100, 1 << 18, 300, 1 << 14, 164, 1e-3, real=True)
 
 
 @pytest.mark.parametrize("d,tmax", [(8, 1 << 21), (16, 1 << 20)])
