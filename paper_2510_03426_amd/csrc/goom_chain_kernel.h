@@ -366,6 +366,11 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
     // convert_items exponentiates it into the tile.
     auto load_items = [&](long long t, int q0, Item<R> (&it)[QB]) {
         const unsigned char *src = left0 + t * a.left_step_stride;
+        // row strides: the template's size where it is known, else opaque to the optimiser, so that the
+        // items' offsets are not carried in registers across the chain's loop
+        int ld = FAST ? DP : d, lfc = a.left_fact_cols;
+        if (!FAST) asm volatile("" : "+s"(ld));
+        asm volatile("" : "+s"(lfc));
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
             const int p = tid + (q0 + q) * NT;
@@ -374,12 +379,12 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
             const bool v1 = FAST || (v0 && (cj + 1 < d));
             if (LEFT_FACT) {
                 // factored left factor: mantissas [DP][left_fact_cols], leading columns on one exponent
-                const R *mp = reinterpret_cast<const R *>(src) + (size_t)row * a.left_fact_cols + cj;
+                const R *mp = reinterpret_cast<const R *>(src) + (size_t)(row * lfc + cj);
                 it[q].re0 = v0 ? mp[0] : (R)0;
                 it[q].re1 = v1 ? mp[1] : (R)0;
                 it[q].im0 = it[q].im1 = (R)0;
             } else {
-                const R *gp = reinterpret_cast<const R *>(src) + ((size_t)row * d + cj) * 2;
+                const R *gp = reinterpret_cast<const R *>(src) + (size_t)(row * ld + cj) * 2;
                 if (FAST || (v1 && vec_ok)) {
                     if (sizeof(R) == 4) {
                         const f4 w = *reinterpret_cast<const f4 *>(gp);
@@ -429,7 +434,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
         }
     };
     // whole factor, no registers kept (start-up, and factors too large to prefetch)
-    auto produce_now = [&](long long t, int buf) {
+    auto produce_now = [&](long long t, int buf) __attribute__((always_inline)) {
 #pragma unroll 1
         for (int q0 = 0; q0 < Q; q0 += QB) {
             Item<R> it[QB];
@@ -534,11 +539,15 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
             }
         }
         if (slab_active) {
+            // the row stride goes through an empty asm so that the DP / 4 offsets of a lane's entries are
+            // worked out here, where they are used, and not kept in (spilled) registers across the chain's loop
+            int fc = a.fact_cols;
+            asm volatile("" : "+s"(fc));
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    mp[(size_t)(16 * kt + Comp<R>::row_of(g, v)) * a.fact_cols + col] = Comp<R>::ldexp_(st[kt][v], shift);
+                    mp[(size_t)((16 * kt + Comp<R>::row_of(g, v)) * fc + col)] = Comp<R>::ldexp_(st[kt][v], shift);
             if (g == 0) ep[col] = e_out;
         }
     };
@@ -621,7 +630,9 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                 const unsigned char *src = left0 + t * a.left_step_stride;
                 const R *mp = reinterpret_cast<const R *>(src);
                 const double *ex = reinterpret_cast<const double *>(src + (size_t)DP * a.left_fact_cols * sizeof(R));
-                R bv = mp[(size_t)i * a.left_fact_cols + d];
+                int lfc = a.left_fact_cols; // opaque, as in load_items
+                asm volatile("" : "+s"(lfc));
+                R bv = mp[(size_t)(i * lfc + d)];
                 if (bv != (R)0) blog = (double)Comp<R>::log2_abs(bv) + ex[d] - ecol;
                 bneg = bv < (R)0;
             }
@@ -661,8 +672,15 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
         R *outp = nullptr;
         if (want_out) {
             long long o_idx = a.out_goom_last_only ? chain_global : (item * a.steps + t0 + t);
-            outp = reinterpret_cast<R *>(a.out_goom) + ((size_t)o_idx * n_rows * m) * 2;
+            // (FAST: the sizes are the template's, so the offsets of a lane's entries are constants and
+            // need no registers across the loop)
+            outp = reinterpret_cast<R *>(a.out_goom) + (FAST ? (size_t)o_idx * (DP * 16 * NW) : (size_t)o_idx * n_rows * m) * 2;
         }
+
+        // (the row stride is made opaque here so that the offsets of a lane's entries are not kept in
+        // registers, which would be spilled, across the loop)
+        int mo = m;
+        if (!FAST) asm volatile("" : "+s"(mo));
 
         // rescale: entry <- entry 2^(n_i - cm), exact; the state's exponent takes cm
         auto rescale = [&](R x, R n_i) {
@@ -670,16 +688,17 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
         };
         if (FAST) {
             if (want_out) { // wave-uniform: one branch around all of this step's stores
+                // the lane's first entry; the others lie at constant distances from it (row_of is linear)
+                R *ob = outp + (Comp<R>::row_of(g, 0) * (16 * NW) + col) * 2;
 #pragma unroll
                 for (int mt = 0; mt < KT; ++mt) {
                     const vec4 nv = *reinterpret_cast<const vec4 *>(&nsh[16 * mt + 4 * g]);
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const int i = 16 * mt + Comp<R>::row_of(g, v);
                         const R x = acc[mt][v];
                         const R re = Comp<R>::out_re(x, nv[v], ecol);
                         const R im = x < (R)0 ? Comp<R>::pi() : (R)0;
-                        R *o = outp + ((size_t)i * m + col) * 2;
+                        R *o = ob + ((16 * mt + Comp<R>::row_of(0, v)) * (16 * NW)) * 2;
                         if (sizeof(R) == 4) {
                             *reinterpret_cast<float2 *>(o) = float2{(float)re, (float)im};
                         } else {
@@ -707,7 +726,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                     if (want_out && i < n_rows) {
                         const R re = Comp<R>::out_re(x, nv[v], ecol);
                         const R im = x < (R)0 ? Comp<R>::pi() : (R)0;
-                        R *o = outp + ((size_t)i * m + col) * 2;
+                        R *o = outp + (size_t)(i * mo + col) * 2;
                         if (sizeof(R) == 4) {
                             *reinterpret_cast<float2 *>(o) = float2{(float)re, (float)im};
                         } else {
@@ -735,7 +754,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                     if (want_out && i < n_rows) {
                         const R re = Comp<R>::out_re(xs, cms, ecol);
                         const R im = xs < (R)0 ? Comp<R>::pi() : (R)0;
-                        R *o = outp + ((size_t)i * m + col) * 2;
+                        R *o = outp + (size_t)(i * mo + col) * 2;
                         o[0] = re;
                         o[1] = im;
                     }
