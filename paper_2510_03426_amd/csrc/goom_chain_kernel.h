@@ -309,7 +309,7 @@ template <typename R> struct Item {
 // quarter of the register file, so four workgroups share a compute unit.
 constexpr int waves_per_simd(int comp_bytes, int dp, int nw)
 {
-    return (comp_bytes == 4 && dp <= 64 && nw >= dp / 16) ? 2 : (comp_bytes == 4 && dp <= 64) ? 2 : 1;
+    return (comp_bytes == 4 && dp <= 64) ? 2 : (comp_bytes == 8 && dp == 64 && nw == 4) ? 2 : 1;
 }
 
 // FAST: the factor fills the padded tile exactly (n = d = DP), the state has whole
