@@ -359,6 +359,12 @@ def test_scan_with_wide_initial_state(G, oracle):
 def test_scan_double_components(G, oracle):
     run_scan_case(G, oracle, 200, 16, 16, seed=4, dtype=np.float64, name="c128 d16")
     run_scan_case(G, oracle, 96, 64, 24, seed=5, dtype=np.float64, name="c128 d64")
+    run_scan_case(G, oracle, 150, 32, 20, seed=6, dtype=np.float64, name="c128 d32")
+    run_scan_case(G, oracle, 36, 128, 8, seed=7, dtype=np.float64, name="c128 d128")
+    # sizes that do not fill the tile (bounds-checked path of the general kernel), with and without an initial state
+    run_scan_case(G, oracle, 40, 100, 9, seed=8, dtype=np.float64, name="c128 d100")
+    run_scan_case(G, oracle, 60, 40, 7, m=40, batch=2, seed=9, dtype=np.float64, name="c128 d40 init")
+    run_scan_case(G, oracle, 50, 20, 6, m=3, seed=10, dtype=np.float64, name="c128 d20 m3")
 
 
 def test_scan_is_deterministic(G, oracle):
