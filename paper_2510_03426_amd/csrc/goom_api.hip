@@ -80,11 +80,12 @@ static int need_ctx(goom_ctx *ctx)
 // that the serial middle phase (one step per chunk) dominates: the serial depth is about
 // 2 * chunk_len + chunks, smallest near chunks = sqrt(2 T).  The 128-wide kernel runs one workgroup
 // per compute unit and the 64-wide one four, and their chains are long, so a partly filled last round
-// of workgroups costs a whole round: there the chain count is one full round (256 or 1024 chains).
-static long long default_chunk_len(long long T, long long batch, long long requested, int dp)
+// of workgroups costs a whole round: there the chain count is one full round (256 or 1024 chains; 512
+// for the 64-wide double kernel, which runs two workgroups per compute unit).
+static long long default_chunk_len(long long T, long long batch, long long requested, int dp, int dtype)
 {
     if (requested > 0) return requested < T ? requested : T;
-    const long long slots = dp >= 128 ? 256 : dp >= 64 ? 1024 : 8192;
+    const long long slots = dp >= 128 ? 256 : dp >= 64 ? (dtype == GOOM_C128 ? 512 : 1024) : 8192;
     long long c_occ = slots / batch; // never more chains than one round holds
     if (c_occ < 1) c_occ = 1;
     long long c_depth = (long long)std::ceil(std::sqrt(2.0 * (double)T));
@@ -129,7 +130,7 @@ static ScanPlan plan_scan(long long T, int d, int m_tot, int m_state, long long 
     // one tile size for every phase (the factored matrices they hand to each other have that many rows): wide
     // enough for the widest state
     p.dp = chain_padded_dim(d, d, m_tot > m_state ? m_tot : m_state);
-    p.L = default_chunk_len(T, batch, requested_chunk, p.dp);
+    p.L = default_chunk_len(T, batch, requested_chunk, p.dp, dtype);
     p.C = (T + p.L - 1) / p.L;
     p.nt = final_only ? p.C : p.C - 1;
     p.tot = fact_layout(p.dp, m_tot, dtype);
