@@ -190,6 +190,45 @@ template <typename R, typename R2> __global__ __launch_bounds__(256) void scaled
     const int per_wave = 64 / group; // vectors a wave handles at a time
     const int sub = lane / group, el = lane % group;
     const int reps = (d + group - 1) / group; // > 1 only when d > 64
+    if (sizeof(R) == 4 && reps == 1) {
+        // float vectors of at most 64 elements, one element per lane: several rounds of vectors per iteration, so
+        // that as many loads per lane are in flight
+        constexpr int U = 2; // (four are no faster: the series in double then bounds the kernel)
+        const R ninf = (R)-__builtin_huge_valf();
+        const size_t round = nwaves * per_wave;
+        for (size_t v0 = wave * per_wave; v0 < nvec; v0 += U * round) {
+            R2 e[U];
+            R m[U];
+            bool live[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const size_t v = v0 + sub + u * round;
+                live[u] = v < nvec && el < d;
+                e[u].x = ninf;
+                e[u].y = (R)0;
+                if (live[u]) e[u] = z[v * d + el];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) m[u] = e[u].x;
+            for (int sft = 1; sft < group; sft <<= 1) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const R o = __shfl_xor(m[u], sft, 64);
+                    m[u] = o > m[u] ? o : m[u];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const size_t v = v0 + sub + u * round;
+                double x = exp_series((double)e[u].x - (double)m[u] + 2.0);
+                x = m[u] > ninf ? x : 0.0;
+                if (odd_multiple_of_pi((double)e[u].y)) x = -x;
+                if (live[u]) out[v * d + el] = (R)x;
+                if (cout && live[u] && el == 0) cout[v] = m[u];
+            }
+        }
+        return;
+    }
     for (size_t v0 = wave * per_wave; v0 < nvec; v0 += nwaves * per_wave) {
         const size_t v = v0 + sub;
         const bool live = v < nvec;
