@@ -1,12 +1,12 @@
 // Chains of matrices with 128 < d <= 256 (paper Section 4.1 runs its chains up to 1024 x 1024;
 // this is the largest size whose running product still fits one compute unit's registers).
 //
-// The state d x m of a chain is split into halves of 128 columns; one workgroup of four waves (one
-// per SIMD, so that a wave may use the whole register file) owns a half, wave w the two 16-column
-// slabs 32 w .. 32 w + 31 of it for all 256 (padded) rows, in the accumulator layout of the
-// 16 x 16 x 4 matrix instruction, so that one step's result is the next step's B operand without
-// moving.  The left factor A_t is exponentiated block by block (32 of its columns at a time, i.e.
-// 32 values of the contraction index) into a double-buffered LDS tile by all 256 threads, the
+// The state d x m of a chain is split into halves of 128 columns; one workgroup of eight waves (two
+// per SIMD, which together use the whole register file: one workgroup per compute unit) owns a half,
+// wave w the 16-column slab 16 w .. 16 w + 15 of it for all 256 (padded) rows, in the accumulator
+// layout of the 16 x 16 x 4 matrix instruction, so that one step's result is the next step's B operand
+// without moving.  The left factor A_t is exponentiated block by block (32 of its columns at a time,
+// i.e. 32 values of the contraction index) into a double-buffered LDS tile by all 512 threads, the
 // block after it waiting in registers; the row shifts n_i of A_t
 // (eq. 10: a whole number near the row's largest log2 magnitude) come from a pass of their own over
 // the input, so a block can be converted before the rest of its rows has been seen.  After the
