@@ -20,6 +20,8 @@
 // (one light pass over the operands): a block whose outputs are all certified returns after it; one
 // with few outputs to repair hands them to its waves one at a time; only a block with many (float
 // components on wide-range data) runs the two sweeps over all sixteen positions per thread.
+#include <type_traits>
+
 #include "goom_chain_kernel.h"
 
 namespace {
@@ -43,6 +45,7 @@ template <> struct Num<float> {
     __device__ static float pi() { return 3.14159274101257324219f; }
     __device__ static float exp2_(float x) { return __builtin_amdgcn_exp2f(x); }
     __device__ static float max_(float x, float y) { return __builtin_fmaxf(x, y); }
+    __device__ static float fma_(float x, float y, float z) { return __builtin_fmaf(x, y, z); }
     __device__ static float log2_(float x) { return ::log2f(x); }
     __device__ static int parity(float im) { return (int)__builtin_rintf(im * 0.318309886183790671538f) & 1; }
 };
@@ -53,6 +56,7 @@ template <> struct Num<double> {
     __device__ static double neg_inf() { return -__builtin_huge_val(); }
     __device__ static double pi() { return 3.14159265358979311600; }
     __device__ static double max_(double x, double y) { return __builtin_fmax(x, y); }
+    __device__ static double fma_(double x, double y, double z) { return __builtin_fma(x, y, z); }
     __device__ static double exp2_(double x) // x <= 0: whole part split off, short series for the rest
     {
         const double k = __builtin_rint(x);
@@ -115,11 +119,11 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
             const int r = e / kJBlock, j = e % kJBlock; // consecutive threads walk along a row of A
             const bool ok = i0 + r < n && j0 + j < d;
             R re = Num<R>::neg_inf();
-            float sg = 0.0f;
+            float sg = 1.0f; // A's sign as +-1, B's as a sign word: one xor gives the factor of a term
             if (ok) {
                 const R *p = Ab + ((size_t)(i0 + r) * d + j0 + j) * 2;
                 re = p[0];
-                sg = Num<R>::parity(p[1]) ? -0.0f : 0.0f;
+                sg = Num<R>::parity(p[1]) ? -1.0f : 1.0f;
             }
             are[r * LDA + j] = re;
             asg[r * LDA + j] = sg;
@@ -284,39 +288,56 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
 #pragma unroll
     for (int q = 0; q < 16; ++q)
         if (__builtin_amdgcn_ballot_w64((need >> q) & 1u) != 0) wave_mask |= 1u << q;
-    R sum[4][4], mxl[4][4];
+    // A term is 2^((x + y) log2(e) + nmx) with nmx = -(mx log2(e)), rounded: one fused multiply-add, whose exponent
+    // is exact, so the sum is the true one times 2^nmx whatever the rounding of nmx, and the result is
+    // (log2|sum| - nmx) ln 2.  (An output with no finite term has all terms zero and stays at -inf.)
+    R sum[4][4], nmx[4][4];
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             sum[r][c] = 0;
-            mxl[r][c] = mx[r][c] > Num<R>::neg_inf() ? mx[r][c] : (R)0;
+            const R mxl = mx[r][c] > Num<R>::neg_inf() ? mx[r][c] : (R)0;
+            nmx[r][c] = -(mxl * Num<R>::kLog2e);
         }
+    // one block of j; ALL: every position is wanted by some lane (wide-range float data), so the sixteen
+    // wave-uniform tests per inner index are left out
+    auto sweep_block = [&](auto all) __attribute__((always_inline)) {
+        constexpr bool ALL = decltype(all)::value;
+#pragma unroll 2
+        for (int j = 0; j < kJBlock; ++j) {
+            R x[4], y[4];
+            float sx[4], sy[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                x[r] = are[(4 * ty + r) * LDA + j];
+                sx[r] = asg[(4 * ty + r) * LDA + j];
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                y[c] = bre[j * kOut + 4 * tx + c];
+                sy[c] = bsg[j * kOut + 4 * tx + c];
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (ALL || (wave_mask & (1u << (4 * r + c)))) {
+                        const R t = Num<R>::exp2_(Num<R>::fma_(x[r] + y[c], Num<R>::kLog2e, nmx[r][c]));
+                        sum[r][c] = Num<R>::fma_(t, flip_sign<R>((R)sx[r], sy[c]), sum[r][c]);
+                    }
+        }
+    };
     for (int j0 = 0; j0 < d; j0 += kJBlock) {
         if (d > kJBlock) stage(j0); // a single block of j is still in LDS
         if (wave_needs) {
-#pragma unroll 2
-            for (int j = 0; j < kJBlock; ++j) {
-                R x[4], y[4];
-                float sx[4], sy[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    x[r] = are[(4 * ty + r) * LDA + j];
-                    sx[r] = asg[(4 * ty + r) * LDA + j];
-                }
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    y[c] = bre[j * kOut + 4 * tx + c];
-                    sy[c] = bsg[j * kOut + 4 * tx + c];
-                }
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-#pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        if (wave_mask & (1u << (4 * r + c))) {
-                            const R t = Num<R>::exp2_(((x[r] + y[c]) - mxl[r][c]) * Num<R>::kLog2e);
-                            sum[r][c] += flip_sign<R>(flip_sign<R>(t, sx[r]), sy[c]);
-                        }
+            if constexpr (sizeof(R) == 4) { // (double components: repairs are rare, and a second copy of the loop costs registers)
+                if (wave_mask == 0xffffu)
+                    sweep_block(std::true_type{});
+                else
+                    sweep_block(std::false_type{});
+            } else {
+                sweep_block(std::false_type{});
             }
         }
     }
@@ -328,8 +349,8 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
                 const int i = i0 + 4 * ty + r, k = k0 + 4 * tx + c;
                 R re_out = Num<R>::neg_inf(), im_out = 0;
                 const R sv = sum[r][c];
-                if (mx[r][c] > Num<R>::neg_inf() && sv != 0) {
-                    re_out = mx[r][c] + Num<R>::log2_(sv < 0 ? -sv : sv) * Num<R>::kLn2;
+                if (sv != 0) {
+                    re_out = (Num<R>::log2_(sv < 0 ? -sv : sv) - nmx[r][c]) * Num<R>::kLn2;
                     im_out = sv < 0 ? Num<R>::pi() : (R)0;
                 }
                 Cb[((size_t)i * m + k) * 2] = re_out;
