@@ -230,6 +230,20 @@ def test_lmme_wide_range_needs_exact_repair(G, oracle, ctype):
                           host(G.lmme(dev(A2), dev(B2), flags=LMME_FAST)).view(np.uint32))
 
 
+@pytest.mark.parametrize("sigma", [22.0, 35.0, 60.0])
+def test_lmme_partly_repaired_blocks(G, oracle, sigma):
+    # moderate ranges: only part of a block's outputs fail the certificate, so the repair kernel runs its
+    # one-wave-per-output list or its sweeps with some of a wave's sixteen positions skipped
+    from paper_2510_03426_amd import LMME_EXACT, LMME_FAST
+    b, n, d, m = 2, 128, 128, 128
+    A, B = si.wide_range_goom_pairs(si.BASE_SEED + 29, b, n, d, m, sigma=sigma, dtype=np.complex64)
+    re, sg, kap = oracle.lmme(A, B, return_kappa=True)
+    fast, got = host(G.lmme(dev(A), dev(B), flags=LMME_FAST)), host(G.lmme(dev(A), dev(B), flags=LMME_EXACT))
+    changed = (fast.view(np.uint32) != got.view(np.uint32)).reshape(b, n, m, 2).any(axis=-1)
+    say(f"lmme sigma {sigma}: the repair pass rewrote {changed.mean():.1%} of the outputs")
+    compare(got, re, sg, kap, name=f"lmme sigma {sigma}", max_ill_fraction=0.02)
+
+
 # -------------------------------------------------------------------------------- scan
 
 def run_scan_case(G, oracle, T, d, chunk_len, m=None, batch=1, seed=0, dtype=np.float32, name=""):
