@@ -14,10 +14,12 @@
 // others are recomputed term by term on the vector ALUs, in two passes over j (maximum, then
 // signed sum of exponentials), which never leaves the representable range.
 //
-// One workgroup handles a 64 x 64 block of outputs of one batch item, a thread 4 x 4 of them, so that
+// Outputs are handled in blocks of 64 x 64 of one batch item, a thread 4 x 4 of them, so that
 // one pair of LDS reads serves sixteen terms; the rows of A and the columns of B are staged in LDS 32
 // inner indices at a time.  The certificate only needs the row maxima of A' and the column maxima of B'
-// (one light pass over the operands): a block whose outputs are all certified returns after it; one
+// (one light pass over the operands, made once by a workgroup for the 128 x 128 outputs = four blocks that
+// it owns, so that the operands of a 128 x 128 x 128 product are read once): a block whose outputs are all
+// certified ends there; one
 // with few outputs to repair hands them to its waves one at a time; only a block with many (float
 // components on wide-range data) runs the two sweeps over all sixteen positions per thread.
 #include <type_traits>
@@ -67,7 +69,12 @@ template <> struct Num<double> {
     __device__ static int parity(double im) { return (int)__builtin_rint(im * 0.318309886183790671538) & 1; }
 };
 
-constexpr int kOut = 64;    // a workgroup owns a 64 x 64 block of outputs, a thread 4 x 4 of them
+constexpr int kOut = 64;    // outputs are worked off in blocks of 64 x 64, a thread 4 x 4 of them
+// Outputs a workgroup owns, kSuper x kSuper.  Double components: 128 (four blocks), the maxima taken once for all
+// of them; repairs are rare there and the pass over the operands is what the kernel costs (config 3: 2.7 -> 2.2 ms).
+// Float components on wide-range data spend their time in the sweeps, and one block per workgroup is faster
+// (4.45 against 4.8 ms).
+template <typename R> constexpr int super_block() { return sizeof(R) == 8 ? 128 : 64; }
 constexpr int kJBlock = 32; // inner indices staged in LDS at a time
 constexpr int kMaxList = 256; // a block with at most this many outputs to repair handles them one by one
 
@@ -81,10 +88,11 @@ template <> __device__ inline double flip_sign<double>(double x, float signword)
     return __builtin_bit_cast(double, __builtin_bit_cast(unsigned long long, x) ^ ((unsigned long long)__builtin_bit_cast(unsigned, signword) << 32));
 }
 
-template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_kernel(ExactArgs a)
+template <typename R> __global__ __launch_bounds__(kThreads, sizeof(R) == 4 ? 4 : 2) void lmme_exact_kernel(ExactArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int n = a.n, d = a.d, m = a.m;
+    constexpr int kSuper = super_block<R>();
     constexpr int LDA = kJBlock + 1; // rows of A: [i][j], padded so that the four rows a wave reads at once differ in bank
     // LDS: log-magnitudes of 64 rows of A [64][33] and 64 columns of B [32][64]; their signs as float +-0
     R *are = reinterpret_cast<R *>(smem);
@@ -94,7 +102,9 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
 
     const int tid = threadIdx.x;
     const int ty = tid / 16, tx = tid % 16;
-    const int blocks_k = (m + kOut - 1) / kOut, blocks_i = (n + kOut - 1) / kOut;
+    // a workgroup owns kSuper x kSuper outputs of one batch item: the maxima are taken once for all of them, then its
+    // (up to) four kOut x kOut blocks are worked off one after the other
+    const int blocks_k = (m + kSuper - 1) / kSuper, blocks_i = (n + kSuper - 1) / kSuper;
     // Workgroups go to the eight XCDs in turn, each with an L2 of its own: renumber them so that the blocks of
     // one batch item (which share rows of A' and columns of B') run on the same XCD, one after the other.
     long long bid = blockIdx.x;
@@ -107,7 +117,8 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
     }
     const long long b = bid / ((long long)blocks_i * blocks_k);
     const int rem = (int)(bid % ((long long)blocks_i * blocks_k));
-    const int i0 = (rem / blocks_k) * kOut, k0 = (rem % blocks_k) * kOut;
+    const int I0 = (rem / blocks_k) * kSuper, K0 = (rem % blocks_k) * kSuper;
+    int i0 = I0, k0 = K0; // the block in hand
     const R *Ab = static_cast<const R *>(a.A) + (size_t)b * n * d * 2;
     const R *Bb = static_cast<const R *>(a.B) + (size_t)b * d * m * 2;
     R *Cb = static_cast<R *>(a.C) + (size_t)b * n * m * 2;
@@ -147,8 +158,13 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
     // ---- row maxima of A' and column maxima of B' over the whole inner index: all the certificate needs.
     // Straight from memory: a wave takes sixteen rows of A' (its lanes along the row, then a reduction across
     // the lanes) and a quarter of the inner indices of B' (its lanes along the 64 columns).
-    __shared__ R s_amax[kOut], s_bmax[kOut], s_part[kThreads / 64][kOut];
-    {
+    __shared__ R s_amax[kSuper], s_bmax[kSuper], s_part[kThreads / 64][kOut];
+    __shared__ int s_count;
+    __shared__ int s_list[kMaxList];
+#pragma unroll 1
+    for (int h = 0; h < kSuper / kOut; ++h) {
+        i0 = I0 + h * kOut;
+        k0 = K0 + h * kOut;
         const int lane = tid & 63, wave = tid >> 6;
         R v[16];
 #pragma unroll
@@ -165,7 +181,7 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
             R w = v[rr];
 #pragma unroll
             for (int sft = 1; sft < 64; sft <<= 1) w = Num<R>::max_(w, (R)__shfl_xor(w, sft, 64));
-            if (lane == 0) s_amax[16 * wave + rr] = w;
+            if (lane == 0) s_amax[h * kOut + 16 * wave + rr] = w;
         }
         R cmaxv = Num<R>::neg_inf();
         const int k = k0 + lane;
@@ -185,15 +201,18 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
             R w = s_part[0][tid];
 #pragma unroll
             for (int u = 1; u < kThreads / 64; ++u) w = Num<R>::max_(w, s_part[u][tid]);
-            s_bmax[tid] = w;
+            s_bmax[h * kOut + tid] = w;
         }
         __syncthreads();
     }
+
+    // ---- one kOut x kOut block: certificate, then the repairs
+    auto repair_block = [&](const R *blk_amax, const R *blk_bmax) __attribute__((always_inline)) {
     R amax[4], bmax[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        amax[r] = s_amax[4 * ty + r];
-        bmax[r] = s_bmax[4 * tx + r];
+        amax[r] = blk_amax[4 * ty + r];
+        bmax[r] = blk_bmax[4 * tx + r];
     }
     // ---- certificate: which outputs of the scaled product may have lost terms to underflow
     unsigned need = 0;
@@ -214,8 +233,7 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
             // a zero row or column gives an exact zero either way
         }
     // the block's outputs to repair, as a list: a short one is worked off output by output
-    __shared__ int s_count;
-    __shared__ int s_list[kMaxList];
+    __syncthreads(); // (the block before this one is done with the list)
     if (tid == 0) s_count = 0;
     __syncthreads();
     for (unsigned rest = need; rest != 0; rest &= rest - 1) {
@@ -356,6 +374,14 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_exact_ker
                 Cb[((size_t)i * m + k) * 2] = re_out;
                 Cb[((size_t)i * m + k) * 2 + 1] = im_out;
             }
+    };
+#pragma unroll 1
+    for (int sb = 0; sb < (kSuper / kOut) * (kSuper / kOut); ++sb) {
+        const int si = sb / (kSuper / kOut), sk = sb % (kSuper / kOut);
+        i0 = I0 + si * kOut;
+        k0 = K0 + sk * kOut;
+        if (i0 < n && k0 < m) repair_block(s_amax + si * kOut, s_bmax + sk * kOut); // (the same for every thread)
+    }
 }
 
 } // namespace
@@ -372,7 +398,8 @@ int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long
     a.n = n;
     a.d = d;
     a.m = m;
-    const long long grid = batch * ((n + kOut - 1) / kOut) * ((m + kOut - 1) / kOut);
+    const int sup = dtype == GOOM_C64 ? super_block<float>() : super_block<double>();
+    const long long grid = batch * ((n + sup - 1) / sup) * ((m + sup - 1) / sup);
     if (grid > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many output blocks for one launch");
     const size_t comp = dtype == GOOM_C64 ? 4 : 8;
     const size_t lds = (size_t)kOut * (kJBlock + 1) * (comp + 4) + (size_t)kJBlock * kOut * (comp + 4) + 64;
