@@ -143,7 +143,10 @@ int goom_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype);
  * Computed as the paper's scaled real product on the matrix cores (eq. 7) with row
  * shifts max_j Re A_ij and column shifts max_j Re B_jk (0 for an all-zero row/column).
  * A sum that is exactly zero gives (-inf, 0).  flags: GOOM_LMME_FAST or GOOM_LMME_EXACT.
- * workspace: goom_lmme_workspace_bytes(...) bytes (may be 0 -> NULL allowed). */
+ * workspace: goom_lmme_workspace_bytes(...) bytes (may be 0 -> NULL allowed).  For n = d = m = 128 with
+ * GOOM_LMME_EXACT the query asks for 256 components per pair, in which the product hands its row and
+ * column shifts to the repair pass; there the workspace is optional (NULL or a smaller one: the repair
+ * pass takes the maxima of the operands itself, more slowly, with the same results within tolerance). */
 int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batch, int n, int d,
               int m, int dtype, uint32_t flags, void *workspace, size_t workspace_bytes);
 size_t goom_lmme_workspace_bytes(int64_t batch, int n, int d, int m, int dtype, uint32_t flags);

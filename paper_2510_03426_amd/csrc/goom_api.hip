@@ -623,10 +623,15 @@ int goom_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype)
 
 static bool lmme_is_large(int n, int d, int m) { return n > GOOM_MAX_DIM || d > GOOM_MAX_DIM || m > GOOM_MAX_DIM; }
 
+// 128 x 128 x 128 products with the repair pass: room for the product's row and column shifts, which spares the repair
+// pass its own pass over the operands (optional: without it the repair pass takes the maxima itself)
+static size_t lmme128_shift_bytes(int64_t batch, int dtype) { return (size_t)batch * 256 * (dtype == GOOM_C64 ? 4 : 8); }
+
 size_t goom_lmme_workspace_bytes(int64_t batch, int n, int d, int m, int dtype, uint32_t flags)
 {
-    (void)flags;
-    if (batch <= 0 || n <= 0 || d <= 0 || m <= 0 || (dtype != GOOM_C64 && dtype != GOOM_C128) || !lmme_is_large(n, d, m)) return 0;
+    if (batch <= 0 || n <= 0 || d <= 0 || m <= 0 || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
+    if (n == 128 && d == 128 && m == 128 && (flags & GOOM_LMME_EXACT)) return lmme128_shift_bytes(batch, dtype);
+    if (!lmme_is_large(n, d, m)) return 0;
     if (n > GOOM_MAX_DIM_LMME || d > GOOM_MAX_DIM_LMME || m > GOOM_MAX_DIM_LMME) return 0;
     return dtype == GOOM_C64 ? lmme_large_workspace_bytes(batch, n, d, m) : lmme_large_f64_workspace_bytes(batch, n, d, m);
 }
@@ -655,8 +660,11 @@ int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batc
     if (int s = need_ctx(ctx)) return s;
     if (n == 128 && d == 128 && m == 128) {
         // the full-size product has a kernel of its own (inner index in tiles, running rescale)
-        if (int s = launch_lmme128(ctx, A, B, C, batch, dtype)) return s;
-        if (flags & GOOM_LMME_EXACT) return launch_lmme_exact(ctx, A, B, C, batch, n, d, m, dtype);
+        void *shifts = nullptr;
+        if ((flags & GOOM_LMME_EXACT) && workspace && aligned(workspace, 16) && workspace_bytes >= lmme128_shift_bytes(batch, dtype))
+            shifts = workspace;
+        if (int s = launch_lmme128(ctx, A, B, C, batch, dtype, shifts)) return s;
+        if (flags & GOOM_LMME_EXACT) return launch_lmme_exact(ctx, A, B, C, batch, n, d, m, dtype, shifts);
         return GOOM_OK;
     }
     const size_t cb = 2 * (dtype == GOOM_C64 ? 4 : 8);

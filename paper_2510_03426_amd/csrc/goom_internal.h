@@ -136,8 +136,11 @@ int run_scan_large(goom_ctx *ctx, const void *M, const void *init, void *P, long
 size_t scan_large_f64_workspace_bytes(long long T, int d, int m, long long batch, long long requested_chunk, bool final_only);
 int run_scan_large_f64(goom_ctx *ctx, const void *M, const void *init, void *P, long long T, int d, int m, long long batch,
                        long long requested_chunk, void *ws, bool final_only);
-int launch_lmme128(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int dtype);
-int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int n, int d, int m, int dtype);
+// shifts: NULL, or [batch][2][128] in the component type: the product's final row and column shifts, written by
+// launch_lmme128 and read by launch_lmme_exact (which otherwise takes the maxima of the operands itself)
+int launch_lmme128(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int dtype, void *shifts);
+int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int n, int d, int m, int dtype,
+                      const void *shifts = nullptr);
 
 int launch_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, uint32_t flags);
 int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype);

@@ -30,6 +30,7 @@ constexpr int kThreads = 512;
 struct Lmme128Args {
     const void *A, *B;
     void *C;
+    void *shifts; // NULL, or per pair the 128 row shifts n_i then the 128 column shifts e_k (for the repair pass)
 };
 
 template <typename R> __global__ __launch_bounds__(kThreads) void lmme_ktile_kernel(Lmme128Args a)
@@ -178,6 +179,12 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_ktile_ker
             op[1] = x < (R)0 ? CR::pi() : (R)0;
         }
     }
+    // the final shifts (whole numbers of log2 units; -1e30 for a row or column without a finite entry), by row and column
+    if (a.shifts) {
+        R *sh = static_cast<R *>(a.shifts) + (size_t)pair * 2 * kD;
+        if (tid < kD) sh[tid] = nsh[CR::phys(tid)];
+        if (g == 0) sh[kD + col] = ecol;
+    }
 }
 
 template <typename R> int launch_ktile(goom_ctx *ctx, const Lmme128Args &args, long long batch)
@@ -200,9 +207,9 @@ template <typename R> int launch_ktile(goom_ctx *ctx, const Lmme128Args &args, l
 
 namespace goom {
 
-int launch_lmme128(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int dtype)
+int launch_lmme128(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int dtype, void *shifts)
 {
-    Lmme128Args args{A, B, C};
+    Lmme128Args args{A, B, C, shifts};
     return dtype == GOOM_C64 ? launch_ktile<float>(ctx, args, batch) : launch_ktile<double>(ctx, args, batch);
 }
 

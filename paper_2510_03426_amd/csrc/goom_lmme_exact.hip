@@ -33,6 +33,7 @@ constexpr int kThreads = kTile * kTile;
 
 struct ExactArgs {
     const void *A, *B;
+    const void *shifts; // NULL, or the product kernel's row and column shifts ([batch][2][128], n = m = 128 only)
     void *C;
     long long batch;
     int n, d, m;
@@ -161,8 +162,17 @@ template <typename R> __global__ __launch_bounds__(kThreads, sizeof(R) == 4 ? 4 
     __shared__ R s_amax[kSuper], s_bmax[kSuper], s_part[kThreads / 64][kOut];
     __shared__ int s_count;
     __shared__ int s_list[kMaxList];
+    const bool given = a.shifts != nullptr; // the shifts come from the product kernel: no pass over the operands
+    if (given) {
+        const R *sh = static_cast<const R *>(a.shifts) + (size_t)b * 256;
+        for (int t = tid; t < kSuper; t += kThreads) {
+            s_amax[t] = sh[I0 + t];
+            s_bmax[t] = sh[128 + K0 + t];
+        }
+        __syncthreads();
+    }
 #pragma unroll 1
-    for (int h = 0; h < kSuper / kOut; ++h) {
+    for (int h = 0; h < (given ? 0 : kSuper / kOut); ++h) {
         i0 = I0 + h * kOut;
         k0 = K0 + h * kOut;
         const int lane = tid & 63, wave = tid >> 6;
@@ -223,10 +233,12 @@ template <typename R> __global__ __launch_bounds__(kThreads, sizeof(R) == 4 ? 4 
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int i = i0 + 4 * ty + r, k = k0 + 4 * tx + c;
-            if (i < n && k < m && amax[r] > Num<R>::neg_inf() && bmax[c] > Num<R>::neg_inf()) {
+            // (given shifts are whole numbers already, with -1e30 for a row or column without a finite entry)
+            const R none = given ? (R)-1.0e29 : Num<R>::neg_inf();
+            if (i < n && k < m && amax[r] > none && bmax[c] > none) {
                 const R cre = Cb[((size_t)i * m + k) * 2];
-                const R ni = __builtin_ceil((double)amax[r] * 1.44269504088896340736);
-                const R ek = __builtin_ceil((double)bmax[c] * 1.44269504088896340736);
+                const R ni = given ? amax[r] : (R)__builtin_ceil((double)amax[r] * 1.44269504088896340736);
+                const R ek = given ? bmax[c] : (R)__builtin_ceil((double)bmax[c] * 1.44269504088896340736);
                 const R scaled = cre * Num<R>::kLog2e - ni - ek; // log2 of the scaled product's magnitude
                 if (!(scaled >= Num<R>::kMargin + log2d + 1)) need |= 1u << (4 * r + c); // also for -inf and NaN
             }
@@ -388,12 +400,15 @@ template <typename R> __global__ __launch_bounds__(kThreads, sizeof(R) == 4 ? 4 
 
 namespace goom {
 
-int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int n, int d, int m, int dtype)
+int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int n, int d, int m, int dtype,
+                      const void *shifts)
 {
+    if (shifts && (n != 128 || m != 128)) return fail(ctx, GOOM_EINVAL, "shifts are handed over for 128 x 128 outputs only");
     ExactArgs a;
     a.A = A;
     a.B = B;
     a.C = C;
+    a.shifts = shifts;
     a.batch = batch;
     a.n = n;
     a.d = d;

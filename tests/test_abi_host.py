@@ -127,6 +127,10 @@ def test_workspace_queries(lib):
     assert lib.goom_affine_scan_scaled_workspace_bytes(65536, 32, 128, 0, None) < aff + 256
     assert lib.goom_affine_scan_scaled_workspace_bytes(65536, 8, 128, 0, None) >= 128 * 65536 * 8 * 8
     assert lib.goom_lmme_workspace_bytes(8192, 128, 128, 128, 0, 0) == 0
+    # with the repair pass: room for the product's 128 row and 128 column shifts per pair (optional for the caller)
+    assert lib.goom_lmme_workspace_bytes(8192, 128, 128, 128, 0, 1) == 8192 * 256 * 4
+    assert lib.goom_lmme_workspace_bytes(8192, 128, 128, 128, 1, 1) == 8192 * 256 * 8
+    assert lib.goom_lmme_workspace_bytes(8192, 128, 128, 64, 0, 1) == 0
     # above 128: scaled operands, their shifts and the transposed product, in the component type
     w32 = lib.goom_lmme_workspace_bytes(2, 1024, 1024, 1024, 0, 0)
     w64 = lib.goom_lmme_workspace_bytes(2, 1024, 1024, 1024, 1, 0)

@@ -223,6 +223,14 @@ def test_lmme_wide_range_needs_exact_repair(G, oracle, ctype):
         assert lost.mean() > 0.5
     got = host(G.lmme(dev(A), dev(B), flags=LMME_EXACT))
     compare(got, re, sg, kap, name=f"lmme exact {np.dtype(ctype).name}", max_ill_fraction=0.02)
+    # the same call through the C ABI without the optional workspace (the repair pass then takes the row and column
+    # maxima itself instead of receiving the product's shifts)
+    import torch
+    from paper_2510_03426_amd import binding as bnd
+    a_d, b_d = dev(A), dev(B)
+    out = torch.empty((b, n, m), dtype=a_d.dtype, device=a_d.device)
+    G._check(G.lib.goom_lmme(G._ctx, bnd._ptr(a_d), bnd._ptr(b_d), bnd._ptr(out), b, n, d, m, bnd._dtype_code(a_d), LMME_EXACT, None, 0))
+    compare(host(out), re, sg, kap, name=f"lmme exact {np.dtype(ctype).name}, no workspace", max_ill_fraction=0.02)
     # benign data: everything certifies, the repair pass changes nothing
     A2 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 27, 7, 2 * 64 * 64).reshape(2, 64, 64))
     B2 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 28, 8, 2 * 64 * 64).reshape(2, 64, 64))
