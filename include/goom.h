@@ -176,6 +176,19 @@ int goom_scan(goom_ctx *ctx, const void *M, const void *init, void *P, int64_t T
 size_t goom_scan_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype,
                                  const goom_scan_opts *opts);
 
+/* goom_scan for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the scan's workspace is a static array of
+ * GOOM_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process ends; the call
+ * itself allocates nothing.  Arguments and results as for goom_scan (same kernels, same launch plan,
+ * bit-identical outputs).  A scan whose goom_scan_workspace_bytes(...) exceeds GOOM_STATIC_SCRATCH_BYTES is
+ * rejected with GOOM_EWORKSPACE and nothing is enqueued (the T = 2^20, d = 64 complex64 scan needs 36.2 MB
+ * and fits).  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two contexts, two threads) race on it and must be serialised by the caller.  Nothing in the array
+ * has to be cleared between calls: every phase writes what the next one reads. */
+#define GOOM_STATIC_SCRATCH_BYTES (40u << 20)
+int goom_scan_static(goom_ctx *ctx, const void *M, const void *init, void *P, int64_t T, int d, int m,
+                     int64_t batch, int dtype, const goom_scan_opts *opts);
+
 /* Only the last prefix: P_final[b] = P[b, T-1] of goom_scan ([batch, d, m]); phases 1 and
  * 2 only, so the input is read once (the product inside the paper's largest-exponent
  * formula, Section 4.2.2, eq. 17). */

@@ -23,7 +23,7 @@ AFFINE_TIME_INVARIANT = 1
 EXPORTS = [
     "goom_version", "goom_create", "goom_destroy", "goom_set_stream", "goom_last_error",
     "goom_status_name", "goom_probe_bandwidth", "goom_probe_matrix_unit", "goom_profile_enable", "goom_profile_count", "goom_profile_get", "goom_to_goom", "goom_from_goom", "goom_lmme", "goom_lmme_workspace_bytes",
-    "goom_scan", "goom_scan_workspace_bytes", "goom_reduce", "goom_reduce_workspace_bytes",
+    "goom_scan", "goom_scan_workspace_bytes", "goom_scan_static", "goom_reduce", "goom_reduce_workspace_bytes",
     "goom_scan_real", "goom_scan_real_workspace_bytes", "goom_reduce_real", "goom_reduce_real_workspace_bytes",
     "goom_scan_reset", "goom_scan_reset_workspace_bytes", "goom_lyapunov_spectrum",
     "goom_lyapunov_spectrum_per_step", "goom_lyapunov_spectrum_per_step_workspace_bytes",
@@ -81,6 +81,7 @@ def load_library():
     lib.goom_scan.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i32, po, vp, sz]
     lib.goom_scan_workspace_bytes.argtypes = [i64, i32, i32, i64, i32, po]
     lib.goom_scan_workspace_bytes.restype = sz
+    lib.goom_scan_static.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i32, po]
     lib.goom_reduce.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i32, po, vp, sz]
     lib.goom_reduce_workspace_bytes.argtypes = [i64, i32, i32, i64, i32, po]
     lib.goom_reduce_workspace_bytes.restype = sz
@@ -271,6 +272,19 @@ class Goom:
         ws, wsn = self.workspace(self.lib.goom_scan_workspace_bytes(T, d, m, batch, code, C.byref(opts)))
         self._check(self.lib.goom_scan(self._ctx, _ptr(mats), _ptr(init), _ptr(out), T, d, m, batch, code,
                                        C.byref(opts), _ptr(ws), wsn))
+        return out
+
+    STATIC_SCRATCH_BYTES = 40 << 20
+
+    def scan_static(self, mats, out, init=None, chunk_len: int = 0):
+        """goom_scan_static: the scan with the library's static scratch array as its workspace.  `out` is the
+        caller's; nothing is allocated here or in the library."""
+        code = _dtype_code(mats)
+        lead, batch, T, d, m = self._scan_shapes(mats, init)
+        assert tuple(out.shape) == tuple(lead + (T, d, m)) and out.dtype == mats.dtype
+        opts = ScanOpts(chunk_len, 0)
+        self._check(self.lib.goom_scan_static(self._ctx, _ptr(mats), _ptr(init), _ptr(out), T, d, m, batch, code,
+                                              C.byref(opts)))
         return out
 
     def reduce(self, mats, init=None, chunk_len: int = 0, out=None):

@@ -2,13 +2,59 @@
 // that turn one call into kernel launches.  No device memory is allocated here.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "goom_internal.h"
 
+// Scratch memory of goom_scan_static, the entry point for callers that cannot allocate: the scan's workspace
+// (chunk products, carries, group products) lives here instead of in a caller-provided buffer.  Every device
+// that loads the library holds its own copy at its own address; in host code the name is only a handle for
+// hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[GOOM_STATIC_SCRATCH_BYTES];
+
 namespace goom {
 
 static thread_local std::string t_error;
+
+// Address of `scratch` on `device`, resolved once per device with that device current.
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[64];
+static bool g_scratch_done[64];
+static std::string g_scratch_err[64];
+
+static void resolve_scratch(goom_ctx *ctx)
+{
+    const int dev = ctx->device;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (dev < 64 && g_scratch_done[dev]) {
+        ctx->scratch = g_scratch_ptr[dev];
+        ctx->scratch_error = g_scratch_err[dev];
+        return;
+    }
+    int prev = -1;
+    void *ptr = nullptr;
+    std::string err;
+    hipError_t e = hipGetDevice(&prev);
+    if (e == hipSuccess) e = hipSetDevice(dev);
+    if (e == hipSuccess) e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) {
+        ptr = nullptr;
+        err = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e);
+        (void)hipGetLastError();
+    } else if (!aligned(ptr, 256)) {
+        ptr = nullptr;
+        err = "static scratch array is not 256-byte aligned";
+    }
+    if (prev >= 0) (void)hipSetDevice(prev);
+    ctx->scratch = ptr;
+    ctx->scratch_error = err;
+    if (dev < 64) {
+        g_scratch_ptr[dev] = ptr;
+        g_scratch_err[dev] = err;
+        g_scratch_done[dev] = true;
+    }
+}
 
 const char *thread_error() { return t_error.c_str(); }
 
@@ -536,6 +582,7 @@ int goom_create(goom_ctx **out, int device, void *stream)
     if (!ctx) return fail(nullptr, GOOM_ENOMEM, "out of host memory");
     ctx->device = device;
     ctx->stream = static_cast<hipStream_t>(stream);
+    resolve_scratch(ctx); // a failure is kept in the context and reported by goom_scan_static
     *out = ctx;
     return GOOM_OK;
 }
@@ -717,6 +764,21 @@ int goom_scan(goom_ctx *ctx, const void *M, const void *init, void *P, int64_t T
               const goom_scan_opts *opts, void *workspace, size_t workspace_bytes)
 {
     return run_scan(ctx, M, init, P, T, d, m, batch, dtype, opts, workspace, workspace_bytes, false);
+}
+
+int goom_scan_static(goom_ctx *ctx, const void *M, const void *init, void *P, int64_t T, int d, int m, int64_t batch, int dtype,
+                     const goom_scan_opts *opts)
+{
+    // argument errors first (reported without a device); the size check uses the same plan as goom_scan
+    if (int s = check_scan_args(ctx, M, P, T, d, m, batch, dtype, opts, GOOM_MAX_DIM_LMME)) return s;
+    const size_t need = goom_scan_workspace_bytes(T, d, m, batch, dtype, opts);
+    if (need > (size_t)GOOM_STATIC_SCRATCH_BYTES)
+        return fail(ctx, GOOM_EWORKSPACE, "this scan needs %zu bytes of scratch memory; goom_scan_static holds %zu (use goom_scan with a workspace)",
+                    need, (size_t)GOOM_STATIC_SCRATCH_BYTES);
+    if (!ctx) return fail(nullptr, GOOM_EINVAL, "null context");
+    if (!ctx->scratch) return fail(ctx, GOOM_EHIP, "%s", ctx->scratch_error.empty() ? "static scratch memory unavailable" : ctx->scratch_error.c_str());
+    // nothing in the workspace has to start at zero: every phase writes what the next one reads
+    return run_scan(ctx, M, init, P, T, d, m, batch, dtype, opts, ctx->scratch, (size_t)GOOM_STATIC_SCRATCH_BYTES, false);
 }
 
 int goom_reduce(goom_ctx *ctx, const void *M, const void *init, void *P_final, int64_t T, int d, int m, int64_t batch,

@@ -23,6 +23,8 @@ struct goom_ctx {
     bool profile = false;
     std::vector<goom_prof_rec> prof;     // records of the last compute call
     std::vector<goom_prof_rec> prof_pool; // events kept for reuse
+    void *scratch = nullptr;              // this device's copy of the library's static scratch array (goom_scan_static)
+    std::string scratch_error;            // why `scratch` could not be resolved, if it could not
 };
 
 namespace goom {

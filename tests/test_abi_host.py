@@ -67,6 +67,11 @@ def test_argument_validation_without_device(lib):
     assert lib.goom_scan(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), C.c_void_p(0x1010), need) == EINVAL
     assert lib.goom_scan(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), p, need) == EINVAL and "context" in err(lib)
     assert lib.goom_reduce(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), None, 0) == EWS
+    # the scan on the library's static scratch array: same argument checks, sizes beyond the array refused
+    assert lib.goom_scan_static(None, p, None, p, 0, 8, 8, 1, 0, C.byref(o)) == EINVAL and "positive" in err(lib)
+    assert lib.goom_scan_static(None, None, None, p, 4, 8, 8, 1, 0, None) == EINVAL
+    assert lib.goom_scan_static(None, p, None, p, 1 << 16, 128, 128, 1, 0, C.byref(ScanOpts(16, 0))) == EWS and "holds" in err(lib)
+    assert lib.goom_scan_static(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o)) == EINVAL and "context" in err(lib)
     # scans of real matrices
     assert lib.goom_scan_real(None, None, None, p, 4, 8, 8, 1, 0, None, None, 0) == EINVAL
     assert lib.goom_scan_real(None, p, None, p, 4096, 64, 64, 1, 0, C.byref(o), None, 0) == EWS
