@@ -2,7 +2,13 @@
 // components: the two kernels its long batched form spends its time in.
 //
 //   * chunk products of the augmented matrices [A | b] (last row implicit): the hot chain
-//     kernel with one more wave for the bias column;
+//     kernel with one more wave for the bias column; for d = 16 and 32 in a variant whose running
+//     product is held in double and multiplied on the double-precision matrix instruction.  A
+//     product of many matrices is all but rank one, and a float product carries its rounding
+//     error relative to its norm: applied to a carried vector that happens to lie nearly
+//     orthogonal to the product's dominant input direction, that error is magnified without
+//     bound.  With double products (and double carries) what reaches the states is the rounding
+//     of the last walk alone, as in a sequential float evaluation;
 //   * the walk that turns the carried vectors into all states: per chunk, h <- A_t h + b_t as a
 //     matrix-vector product.  One wave owns one chunk.  A lane loads adjacent entries of a
 //     row of A_t (four lanes share a row, sixteen rows are handled per pass), scales
@@ -78,13 +84,23 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
             iidx = (item * a.init_ngroups + grp) * (a.init_group + 1) + (chunk - grp * a.init_group);
         }
         const unsigned char *ip = a.init + iidx * a.init_stride;
-        const float *mp = reinterpret_cast<const float *>(ip);
-        eh = *reinterpret_cast<const double *>(ip + (size_t)DP * a.fact_cols * sizeof(float));
         bool nz = false;
+        if (a.fact_f64) { // carries with double mantissas (scaled to at most 1 in magnitude, so the conversion is safe)
+            const double *mp = reinterpret_cast<const double *>(ip);
+            eh = *reinterpret_cast<const double *>(ip + (size_t)DP * a.fact_cols * sizeof(double));
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-            hm[e] = mp[(size_t)(c0 + e) * a.fact_cols];
-            nz = nz || hm[e] != 0.0f;
+            for (int e = 0; e < EPL; ++e) {
+                hm[e] = (float)mp[(size_t)(c0 + e) * a.fact_cols];
+                nz = nz || hm[e] != 0.0f;
+            }
+        } else {
+            const float *mp = reinterpret_cast<const float *>(ip);
+            eh = *reinterpret_cast<const double *>(ip + (size_t)DP * a.fact_cols * sizeof(float));
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                hm[e] = mp[(size_t)(c0 + e) * a.fact_cols];
+                nz = nz || hm[e] != 0.0f;
+            }
         }
         // a zero vector carries no meaningful exponent
         if (__builtin_amdgcn_ballot_w64(nz) == 0 || !(__builtin_fabs(eh) < 1.0e15)) eh = 0.0;
@@ -135,9 +151,16 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
 #pragma unroll
             for (int e = 0; e < EPL; ++e) {
                 // exponent argument with one rounding at its own (small) magnitude, then the low part of log2(e)
-                float t = __builtin_fmaf(re[e], kHi, -nsub);
-                t = __builtin_fmaf(re[e], kLo, t);
-                const float v = __builtin_amdgcn_exp2f(t); // 2^-inf = 0 covers zero entries and zero rows
+                float v;
+                if (TI) {
+                    // converted once and applied at every step: its rounding is the same at every step and adds up
+                    // along the chain, so the one conversion is made in double and rounded once
+                    v = zero_row ? 0.0f : (float)Comp<double>::exp2_shifted((double)re[e], (double)n);
+                } else {
+                    float t = __builtin_fmaf(re[e], kHi, -nsub);
+                    t = __builtin_fmaf(re[e], kLo, t);
+                    v = __builtin_amdgcn_exp2f(t); // 2^-inf = 0 covers zero entries and zero rows
+                }
                 const float kf = __builtin_fmaf(im[e], 0.318309886183790671538f, 12582912.0f);
                 sv[q][e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) ^ (__builtin_bit_cast(int, kf) << 31));
             }
@@ -254,28 +277,339 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
     if (a.out_fact_final) {
         // the chunk's vector as column bias_col of the chunk's factored total, with its own exponent
         unsigned char *dst = a.out_fact_final + (item * a.chunks_per_item + chunk) * a.fact_stride;
-        float *mp = reinterpret_cast<float *>(dst);
-        double *ep = reinterpret_cast<double *>(dst + (size_t)DP * a.fact_cols * sizeof(float));
-        if (rsub == 0) {
+        if (a.fact_f64) {
+            double *mp = reinterpret_cast<double *>(dst);
+            double *ep = reinterpret_cast<double *>(dst + (size_t)DP * a.fact_cols * sizeof(double));
+            if (rsub == 0) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) mp[(size_t)(c0 + e) * a.fact_cols + a.bias_col] = hm[e];
+                for (int e = 0; e < EPL; ++e) mp[(size_t)(c0 + e) * a.fact_cols + a.bias_col] = (double)hm[e];
+            }
+            if (lane == 0) ep[a.bias_col] = eh;
+        } else {
+            float *mp = reinterpret_cast<float *>(dst);
+            double *ep = reinterpret_cast<double *>(dst + (size_t)DP * a.fact_cols * sizeof(float));
+            if (rsub == 0) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) mp[(size_t)(c0 + e) * a.fact_cols + a.bias_col] = hm[e];
+            }
+            if (lane == 0) ep[a.bias_col] = eh;
         }
-        if (lane == 0) ep[a.bias_col] = eh;
     }
+}
+
+
+// Chunk products [A* | b*] with the running product in double (float GOOM factors, double factored result).
+// The factor is exponentiated into a float LDS tile exactly as in the hot kernel; A operands are widened when
+// they are read.  The double-precision 16 x 16 x 4 instruction leaves rows 4 v + g of a column in register v of
+// lane group g and takes row g of its B operand from lane group g, so the accumulators are again the next
+// step's B operands if contraction index 16 kt + 4 v + g sits at position 16 kt + 4 g + v of a tile row
+// (Comp<double>::phys); the row exponents and the bias wave's column are stored in the same order.
+// a.bias == NULL: no bias is added (the column stays zero), which gives plain matrix powers and products.
+// PRECISE: every entry of the tile is exponentiated in double and rounded once (for one matrix applied at every
+// step, whose conversion error would otherwise be the same at every step and add up along the chain).
+template <int DP, int NW, bool PRECISE>
+__global__ __launch_bounds__((NW + 1) * 64, 4) void affine_chunk_f64_kernel(ChainArgs a)
+{
+    typedef Comp<float> C;
+    typedef Comp<double> CD;
+    constexpr int KT = DP / 16;
+    constexpr int LDA = DP + 4;
+    constexpr int NWT = NW + 1;
+    constexpr int NT = NW * 64;  // threads that convert the factor
+    constexpr int LPR = DP / 4;  // lanes per row of the factor
+    constexpr int NITEMS = DP * LPR;
+    constexpr int Q = NITEMS / NT;
+    constexpr int kRenormEvery = 4;
+    static_assert(NITEMS % NT == 0 && NT % LPR == 0 && NW == KT, "tile does not divide among the threads");
+    constexpr size_t kTileBytes = (size_t)DP * LDA * sizeof(float);
+    constexpr size_t kBufBytes = kTileBytes + (size_t)DP * sizeof(float);
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    auto tile_of = [&](int b) { return reinterpret_cast<float *>(smem + (size_t)b * kBufBytes); };
+    auto nsh_of = [&](int b) { return reinterpret_cast<float *>(smem + (size_t)b * kBufBytes + kTileBytes); };
+    double *wave_red = reinterpret_cast<double *>(smem + 2 * kBufBytes);
+    double *wvec = reinterpret_cast<double *>(smem + 2 * kBufBytes + 128); // the bias wave's column, in tile column order
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4;
+    const int c = lane & 15;
+    const int col = wave * 16 + c;
+    const int c4 = 4 * (tid % LPR);                      // first of this lane's four factor columns
+    const int p4 = (c4 & ~15) | ((c4 >> 2) & 3);         // position of column c4 in a tile row; c4 + e sits 4 e further on
+    const bool bias_wave = wave == NW;
+    const bool converter = !bias_wave;
+    const bool has_bias = a.bias != nullptr;
+    constexpr int LPRB = 64 / DP; // bias wave: lanes per row
+    constexpr int CPLB = DP / LPRB;
+    const int brow = lane / LPRB;
+    const int bc0 = CPLB * (lane % LPRB);
+
+    const long long chain = blockIdx.x;
+    const long long item = chain / a.chunks_launched;
+    const long long chunk = chain % a.chunks_launched;
+    const long long t0 = chunk * a.chunk_len;
+    long long len = a.steps - t0;
+    if (len > a.chunk_len) len = a.chunk_len;
+    const long long chain_global = item * a.chunks_per_item + chunk;
+    const unsigned char *left0 = a.left + item * a.left_batch_stride + t0 * a.left_step_stride;
+
+    auto load_items = [&](long long t, Item4 (&it)[Q]) {
+        const float *src = reinterpret_cast<const float *>(left0 + t * a.left_step_stride);
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const int row = (tid + q * NT) / LPR;
+            const f4 *gp = reinterpret_cast<const f4 *>(src + ((size_t)row * DP + c4) * 2);
+            it[q].a = gp[0];
+            it[q].b = gp[1];
+        }
+    };
+    // tile[i][phys(j)] = (+-) 2^(log2|A_ij| + r_j - n_i), n_i = ceil(max_j (log2|A_ij| + r_j)); r_j: the row
+    // exponents still attached to the running product (zero at the start)
+    auto convert_items = [&](const Item4 (&it)[Q], int buf, const float *rsrc) {
+        const float kHi = 1.44269502162933349609375f;
+        const float kLo = 1.925963033500011e-8f;
+        float *tile = tile_of(buf);
+        float *nsh = nsh_of(buf);
+        float rj[4] = {0.f, 0.f, 0.f, 0.f};
+        if (rsrc) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) rj[e] = rsrc[p4 + 4 * e];
+        }
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const int row = (tid + q * NT) / LPR;
+            const float re[4] = {it[q].a[0], it[q].a[2], it[q].b[0], it[q].b[2]};
+            const float im[4] = {it[q].a[1], it[q].a[3], it[q].b[1], it[q].b[3]};
+            float u = __builtin_fmaf(re[0], kHi, rj[0]);
+#pragma unroll
+            for (int e = 1; e < 4; ++e) u = vmax_raw(u, __builtin_fmaf(re[e], kHi, rj[e]));
+            int key = C::key_of(u);
+            key = C::imax(key, C::dpp<0xB1>(key));
+            if (LPR >= 4) key = C::imax(key, C::dpp<0x4E>(key));
+            if (LPR >= 8) key = C::imax(key, C::dpp<0x141>(key));
+            const float mx = C::of_key(key);
+            const bool zero_row = !(mx > -1.0e30f);
+            const float n = zero_row ? 0.0f : __builtin_ceilf(mx); // (the bias is scaled by the shift: it stays small for a zero row)
+            const float nsub = zero_row ? __builtin_huge_valf() : n;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float v;
+                if (PRECISE) {
+                    v = zero_row ? 0.0f : (float)CD::exp2_shifted((double)re[e], (double)(n - rj[e]));
+                } else {
+                    float t = __builtin_fmaf(re[e], kHi, rj[e] - nsub);
+                    t = __builtin_fmaf(re[e], kLo, t);
+                    v = __builtin_amdgcn_exp2f(t);
+                }
+                const float kf = __builtin_fmaf(im[e], 0.318309886183790671538f, 12582912.0f);
+                tile[row * LDA + p4 + 4 * e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) ^ (__builtin_bit_cast(int, kf) << 31));
+            }
+            nsh[CD::phys(row)] = n; // every lane of the row writes the same value
+        }
+    };
+
+    // state: st[kt][v] = W[16 kt + 4 v + g][col]; identity at the start, the bias column zero
+    double st[KT][4];
+    double ecol = 0.0;
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) st[kt][v] = (a.init_mode == 0 && 16 * kt + 4 * v + g == col) ? 1.0 : 0.0;
+
+    Item4 pre[Q];
+    if (len > 0 && converter) {
+        load_items(0, pre);
+        convert_items(pre, 0, nullptr);
+        if (len > 1) load_items(1, pre);
+    }
+    float2 bpre = {-__builtin_huge_valf(), 0.0f};
+    auto load_bias = [&](long long t) {
+        if (has_bias) bpre = *reinterpret_cast<const float2 *>(a.bias + ((size_t)(item * a.steps + t0 + t) * DP + brow) * 8);
+    };
+    if (bias_wave && lane < DP) wvec[lane] = 0.0;
+    if (bias_wave && len > 0) load_bias(0);
+    __syncthreads();
+
+    for (long long t = 0; t < len; ++t) {
+        const int cur = (int)(t & 1);
+        const float *tile = tile_of(cur);
+        const float *nsh = nsh_of(cur);
+        const bool last = t == len - 1;
+
+        d4 acc[KT];
+        double accb = 0.0;
+        if (bias_wave) {
+            // column d of the product: row brow of the tile times the column, on the vector ALU
+#pragma unroll
+            for (int k = 0; k < CPLB / 4; ++k) {
+                const f4 av = *reinterpret_cast<const f4 *>(&tile[brow * LDA + bc0 + 4 * k]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) accb = __builtin_fma((double)av[e], wvec[bc0 + 4 * k + e], accb);
+            }
+#pragma unroll
+            for (int s = 1; s < LPRB; s <<= 1) accb += __shfl_xor(accb, s, 64);
+        } else {
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) acc[mt] = d4{0, 0, 0, 0};
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt) {
+                f4 av[KT];
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+                    av[mt] = *reinterpret_cast<const f4 *>(&tile[(16 * mt + c) * LDA + 16 * kt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int mt = 0; mt < KT; ++mt) acc[mt] = CD::mfma((double)av[mt][v], st[kt][v], acc[mt]);
+            }
+        }
+        if (converter && !last) {
+            convert_items(pre, cur ^ 1, nsh);
+            load_items(t + 2 < len ? t + 2 : len - 1, pre);
+        }
+        float nrb = 0.0f;
+        if (bias_wave) {
+            // b_i enters entry (i, d) of the product, held as accb 2^(n_i + ecol): add (+-) 2^(log2|b_i| - n_i - ecol).
+            // Should the column have shrunk so far below the bias that this would overflow, it is scaled down first.
+            nrb = nsh[CD::phys(brow)];
+            const float x = (float)__builtin_fma((double)bpre.x, kLog2e, -((double)nrb + ecol)); // -inf for a zero entry or no bias
+            float down = 0.0f;
+            if (__builtin_amdgcn_ballot_w64(x > 64.0f) != 0) {
+                const float amax = C::template group_allmax<64>(x, x);
+                down = C::max_(0.0f, __builtin_ceilf(amax) - 64.0f);
+                accb = __builtin_ldexp(accb, -(int)C::clamp_shift(down));
+                ecol += (double)down;
+            }
+            accb += (double)C::apply_sign(__builtin_amdgcn_exp2f(x - down), bpre.y);
+            load_bias(t + 1 < len ? t + 1 : len - 1);
+        }
+
+        // state for the next step: the raw product (its row exponents n_i go to the next factor's columns),
+        // columns renormalised every few steps; after the last step the row exponents are folded in
+        if (bias_wave) {
+            if (!last) {
+                if ((t % kRenormEvery) == kRenormEvery - 1) {
+                    float cm = accb != 0.0 ? (float)CD::frexp_exp(accb) : -1.0e30f;
+                    cm = C::template group_allmax<64>(cm, cm);
+                    if (!(cm > -1.0e29f)) cm = 0.0f; // a zero column keeps its exponent
+                    accb = __builtin_ldexp(accb, -(int)cm);
+                    ecol += (double)cm;
+                }
+            } else {
+                float cm = accb != 0.0 ? (float)CD::frexp_exp(accb) + nrb : -1.0e30f;
+                cm = C::template group_allmax<64>(cm, cm);
+                if (!(cm > -1.0e29f)) cm = 0.0f; // a zero column
+                accb = __builtin_ldexp(accb, (int)C::clamp_shift(nrb - cm));
+                ecol += (double)cm;
+            }
+            if (lane % LPRB == 0) wvec[CD::phys(brow)] = accb;
+        } else if (!last) {
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) st[mt][v] = acc[mt][v];
+            if ((t % kRenormEvery) == kRenormEvery - 1) {
+                float cm = -1.0e30f;
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) cm = C::max_(cm, st[mt][v] != 0.0 ? (float)CD::frexp_exp(st[mt][v]) : -1.0e30f);
+                cm = C::xor16_32_max(cm);
+                if (!(cm > -1.0e29f)) cm = 0.0f;
+                const int sh = -(int)cm;
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) st[mt][v] = __builtin_ldexp(st[mt][v], sh);
+                ecol += (double)cm;
+            }
+        } else {
+            float cm = -1.0e30f;
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                const f4 nv = *reinterpret_cast<const f4 *>(&nsh[16 * mt + 4 * g]); // nv[v]: row 16 mt + 4 v + g
+#pragma unroll
+                for (int v = 0; v < 4; ++v) cm = C::max_(cm, acc[mt][v] != 0.0 ? (float)CD::frexp_exp(acc[mt][v]) + nv[v] : -1.0e30f);
+            }
+            cm = C::xor16_32_max(cm);
+            if (!(cm > -1.0e29f)) cm = 0.0f;
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                const f4 nv = *reinterpret_cast<const f4 *>(&nsh[16 * mt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) st[mt][v] = __builtin_ldexp(acc[mt][v], (int)C::clamp_shift(nv[v] - cm));
+            }
+            ecol += (double)cm;
+        }
+        __syncthreads();
+    }
+
+    if (a.out_fact_final) {
+        // factored product of the chunk: double mantissas [DP][fact_cols], the columns of A* on one exponent (it
+        // becomes a left factor), the bias column on its own
+        unsigned char *dst = a.out_fact_final + chain_global * a.fact_stride;
+        double *mp = reinterpret_cast<double *>(dst);
+        double *ep = reinterpret_cast<double *>(dst + (size_t)DP * a.fact_cols * sizeof(double));
+        double cmx = 0.0;
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) cmx = CD::max_(cmx, __builtin_fabs(st[kt][v]));
+        cmx = CD::xor16_32_max(cmx);
+        double ev = (cmx > 0.0 && !bias_wave) ? ecol : kNegBig;
+#pragma unroll
+        for (int s = 1; s < 16; s <<= 1) {
+            const double o = shfl_xor_double(ev, s);
+            ev = o > ev ? o : ev;
+        }
+        if (lane == 0) wave_red[wave] = ev;
+        __syncthreads();
+        double emax = kNegBig;
+        for (int w = 0; w < NWT; ++w) emax = wave_red[w] > emax ? wave_red[w] : emax;
+        if (emax == kNegBig) emax = 0.0;
+        double dsh = ecol - emax;
+        dsh = dsh > -4000.0 ? dsh : -4000.0;
+        const int shift = (cmx > 0.0 && !bias_wave) ? (int)dsh : 0;
+        if (bias_wave) {
+            if (lane % LPRB == 0) mp[(size_t)brow * a.fact_cols + DP] = wvec[CD::phys(brow)];
+            for (int idx = lane; idx < DP * 15; idx += 64) mp[(size_t)(idx / 15) * a.fact_cols + DP + 1 + idx % 15] = 0.0;
+        } else {
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    mp[(size_t)(16 * kt + 4 * v + g) * a.fact_cols + col] = __builtin_ldexp(st[kt][v], shift);
+        }
+        if (g == 0) ep[col] = bias_wave ? ecol : emax;
+    }
+}
+
+template <int DP, int NW, bool PRECISE> int launch_chunk_f64(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
+{
+    constexpr int LDA = DP + 4;
+    const size_t lds = 2 * ((size_t)DP * LDA * sizeof(float) + (size_t)DP * sizeof(float)) + 128 + DP * sizeof(double);
+    if (grid <= 0) return GOOM_OK;
+    if (grid > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many chains for one launch (%lld)", grid);
+    goom::prof_begin(ctx, label);
+    hipLaunchKernelGGL((affine_chunk_f64_kernel<DP, NW, PRECISE>), dim3((unsigned)grid), dim3((NW + 1) * 64), lds, ctx->stream, args);
+    goom::prof_end(ctx);
+    return goom::check_hip(ctx, hipGetLastError(), "launch affine_chunk_f64_kernel");
 }
 
 // Time-invariant recurrence: every chunk's total is [A^L | b*_c].  A^L has been written to the first
 // chunk's slot of each batch item; this copies it to the other chunks and clears the padding columns
 // (column d, the bias, is written by the walk kernel).
-__global__ __launch_bounds__(256) void replicate_power_kernel(unsigned char *totals, long long stride, int fact_cols, int dp, int d,
+template <typename R> __global__ __launch_bounds__(256) void replicate_power_kernel(unsigned char *totals, long long stride, int fact_cols, int dp, int d,
                                                               long long chunks, long long chunks_per_item)
 {
     const long long item = blockIdx.x / chunks, chunk = blockIdx.x % chunks;
     const unsigned char *src = totals + (item * chunks_per_item) * stride;
     unsigned char *dst = totals + (item * chunks_per_item + chunk) * stride;
-    const float *sm = reinterpret_cast<const float *>(src);
-    float *dm = reinterpret_cast<float *>(dst);
-    const size_t mant = (size_t)dp * fact_cols * sizeof(float);
+    const R *sm = reinterpret_cast<const R *>(src);
+    R *dm = reinterpret_cast<R *>(dst);
+    const size_t mant = (size_t)dp * fact_cols * sizeof(R);
     const double *se = reinterpret_cast<const double *>(src + mant);
     double *de = reinterpret_cast<double *>(dst + mant);
     for (int e = threadIdx.x; e < dp * fact_cols; e += 256) {
@@ -283,7 +617,7 @@ __global__ __launch_bounds__(256) void replicate_power_kernel(unsigned char *tot
         if (col < d) {
             if (chunk != 0) dm[e] = sm[e];
         } else if (col > d) {
-            dm[e] = 0.0f;
+            dm[e] = (R)0;
         }
     }
     for (int col = threadIdx.x; col < fact_cols; col += 256) {
@@ -344,14 +678,29 @@ int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long
     return ti ? launch_walk<32, true>(ctx, args, nchains, label) : launch_walk<32, false>(ctx, args, nchains, label);
 }
 
+// the double-state chunk products: same conditions as affine_chunk_applies, the result in double (d = 16, 32)
+int dispatch_affine_chunk_f64(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label)
+{
+    if (!((dp == 16 || dp == 32) && args.n == dp && args.d == dp && args.m == dp + 1 && args.init_mode == 0 && args.out_goom == nullptr &&
+          args.out_fact_steps == nullptr && args.out_fact_final != nullptr && args.fact_cols == dp + 16))
+        return goom::fail(ctx, GOOM_EUNSUPPORTED, "double-state chunk products are built for d = 16 and 32");
+    if (args.left_step_stride == 0) // one matrix at every step
+        return dp == 16 ? launch_chunk_f64<16, 1, true>(ctx, args, grid, label) : launch_chunk_f64<32, 2, true>(ctx, args, grid, label);
+    return dp == 16 ? launch_chunk_f64<16, 1, false>(ctx, args, grid, label) : launch_chunk_f64<32, 2, false>(ctx, args, grid, label);
+}
+
 int launch_replicate_power(goom_ctx *ctx, void *totals, long long stride, int fact_cols, int dp, int d, long long batch,
-                           long long chunks, long long chunks_per_item)
+                           long long chunks, long long chunks_per_item, bool f64)
 {
     const long long grid = batch * chunks;
     if (grid <= 0) return GOOM_OK;
     if (grid > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many chunks for one launch");
-    hipLaunchKernelGGL(replicate_power_kernel, dim3((unsigned)grid), dim3(256), 0, ctx->stream, static_cast<unsigned char *>(totals), stride,
-                       fact_cols, dp, d, chunks, chunks_per_item);
+    if (f64)
+        hipLaunchKernelGGL(replicate_power_kernel<double>, dim3((unsigned)grid), dim3(256), 0, ctx->stream, static_cast<unsigned char *>(totals),
+                           stride, fact_cols, dp, d, chunks, chunks_per_item);
+    else
+        hipLaunchKernelGGL(replicate_power_kernel<float>, dim3((unsigned)grid), dim3(256), 0, ctx->stream, static_cast<unsigned char *>(totals),
+                           stride, fact_cols, dp, d, chunks, chunks_per_item);
     return goom::check_hip(ctx, hipGetLastError(), "launch replicate_power_kernel");
 }
 

@@ -172,18 +172,21 @@ struct ScanPlan {
     size_t total() const { return tot_bytes + car_bytes + gtot_bytes + gcar_bytes; }
 };
 
+// fact_dtype: component type of the factored matrices in the workspace when it differs from the GOOMs' (the float
+// recurrence keeps its chunk products and carries in double)
 static ScanPlan plan_scan(long long T, int d, int m_tot, int m_state, long long batch, int dtype,
-                          long long requested_chunk, bool final_only)
+                          long long requested_chunk, bool final_only, int fact_dtype = -1)
 {
     ScanPlan p;
+    if (fact_dtype < 0) fact_dtype = dtype;
     // one tile size for every phase (the factored matrices they hand to each other have that many rows): wide
     // enough for the widest state
     p.dp = chain_padded_dim(d, d, m_tot > m_state ? m_tot : m_state);
     p.L = default_chunk_len(T, batch, requested_chunk, p.dp, dtype);
     p.C = (T + p.L - 1) / p.L;
     p.nt = final_only ? p.C : p.C - 1;
-    p.tot = fact_layout(p.dp, m_tot, dtype);
-    p.car = fact_layout(p.dp, m_state, dtype);
+    p.tot = fact_layout(p.dp, m_tot, fact_dtype);
+    p.car = fact_layout(p.dp, m_state, fact_dtype);
     p.S = 0;
     p.G = 0;
     if (p.nt > 96) {
@@ -836,12 +839,35 @@ int goom_reduce_real(goom_ctx *ctx, const void *X, const void *init, void *P_fin
     return run_scan_real(ctx, X, init, P_final, T, d, m, batch, dtype, opts, workspace, workspace_bytes, true);
 }
 
+// The float recurrence with d = 16 or 32 keeps its chunk products and carries in double: a float product of many
+// matrices carries its rounding error relative to its norm, and applied to a carried vector that lies nearly
+// orthogonal to the product's dominant input direction that error has no bound relative to the result.
+struct AffinePlan {
+    ScanPlan p;
+    bool f64;        // chunk products and carries in double (float GOOMs in and out)
+    size_t h0_bytes; // room for an initial state widened to double components
+    size_t total() const { return align_up(p.total(), 256) + h0_bytes; }
+};
+
+static AffinePlan plan_affine(long long T, int d, long long batch, int dtype, const goom_scan_opts *opts)
+{
+    AffinePlan ap;
+    const long long req = opts ? opts->chunk_len : 0;
+    ap.p = plan_scan(T, d, d + 1, 1, batch, dtype, req, false);
+    ap.f64 = dtype == GOOM_C64 && (d == 16 || d == 32) && ap.p.dp == d && ap.p.C > 1;
+    ap.h0_bytes = 0;
+    if (ap.f64) {
+        ap.p = plan_scan(T, d, d + 1, 1, batch, dtype, req, false, GOOM_C128);
+        ap.h0_bytes = align_up((size_t)batch * d * 16, 256);
+    }
+    return ap;
+}
+
 size_t goom_affine_scan_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts)
 {
     if (T <= 0 || d <= 0 || batch <= 0 || d >= GOOM_MAX_DIM) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
-    ScanPlan p = plan_scan(T, d, d + 1, 1, batch, dtype, opts ? opts->chunk_len : 0, false);
-    return p.total();
+    return plan_affine(T, d, batch, dtype, opts).total();
 }
 
 // Scaled states (eq. 21) come straight out of the matrix-vector walk where that kernel serves the
@@ -857,8 +883,8 @@ size_t goom_affine_scan_scaled_workspace_bytes(int64_t T, int d, int64_t batch, 
 {
     if (T <= 0 || d <= 0 || batch <= 0 || d >= GOOM_MAX_DIM) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
-    const ScanPlan p = plan_scan(T, d, d + 1, 1, batch, dtype, opts ? opts->chunk_len : 0, false);
-    return align_up(p.total(), 256) + (affine_scaled_is_fused(p, d, dtype) ? 0 : affine_states_bytes(T, d, batch, dtype));
+    const AffinePlan ap = plan_affine(T, d, batch, dtype, opts);
+    return align_up(ap.total(), 256) + (affine_scaled_is_fused(ap.p, d, dtype) ? 0 : affine_states_bytes(T, d, batch, dtype));
 }
 
 static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H, void *scaled, void *logscale,
@@ -873,18 +899,20 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
     if (d >= GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "the recurrence with bias needs d < %d", GOOM_MAX_DIM);
     if (!aligned(bias, 16) || (h0 && !aligned(h0, 16))) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
     if (logscale && !aligned(logscale, comp_bytes(dtype))) return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
-    const ScanPlan p = plan_scan(T, d, d + 1, 1, batch, dtype, opts ? opts->chunk_len : 0, false);
+    const AffinePlan ap = plan_affine(T, d, batch, dtype, opts);
+    const ScanPlan &p = ap.p;
     const bool fused = want_scaled && affine_scaled_is_fused(p, d, dtype);
-    const size_t need = want_scaled ? align_up(p.total(), 256) + (fused ? 0 : affine_states_bytes(T, d, batch, dtype)) : p.total();
+    const size_t need = want_scaled ? align_up(ap.total(), 256) + (fused ? 0 : affine_states_bytes(T, d, batch, dtype)) : ap.total();
     if (int s = check_workspace(ctx, ws, ws_bytes, need)) return s;
     if (int s = need_ctx(ctx)) return s;
     const size_t cb = 2 * comp_bytes(dtype);
     if (want_scaled && !fused) {
         // the states as GOOMs behind the scan's own workspace, then their scaled exponentials
-        H = static_cast<unsigned char *>(ws) + align_up(p.total(), 256);
-        if (int s = run_affine(ctx, A, bias, h0, H, nullptr, nullptr, T, d, batch, dtype, opts, ws, p.total())) return s;
+        H = static_cast<unsigned char *>(ws) + align_up(ap.total(), 256);
+        if (int s = run_affine(ctx, A, bias, h0, H, nullptr, nullptr, T, d, batch, dtype, opts, ws, ap.total())) return s;
         return launch_scaled_exp(ctx, H, scaled, logscale, (size_t)batch * (size_t)T, d, dtype);
     }
+    const int f64 = ap.f64 ? 1 : 0;
 
     ChainLaunch base;
     std::memset(&base, 0, sizeof base);
@@ -932,8 +960,13 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
         l.fact_stride = (long long)p.tot.stride * p.C;
         l.fact_cols = p.tot.cols_padded;
         l.label = "affine_phase1_matrix_power";
+        if (f64) { // the double-state chunk kernel with no bias: [A^L | 0]
+            l.acc_f64 = 1;
+            l.m = d + 1;
+            l.bias_col = d;
+        }
         if (int s = launch_chain(ctx, l)) return s;
-        if (int s = goom_chain::launch_replicate_power(ctx, totals, (long long)p.tot.stride, p.tot.cols_padded, p.dp, d, batch, p.C - 1, p.C)) return s;
+        if (int s = goom_chain::launch_replicate_power(ctx, totals, (long long)p.tot.stride, p.tot.cols_padded, p.dp, d, batch, p.C - 1, p.C, f64 != 0)) return s;
         ChainLaunch w = base;
         w.m = 1;
         w.bias_col = d;
@@ -943,6 +976,7 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
         w.out_fact_final = totals;
         w.fact_stride = (long long)p.tot.stride;
         w.fact_cols = p.tot.cols_padded;
+        w.fact_f64 = f64;
         w.label = "affine_phase1_chunk_vectors";
         if (int s = launch_chain(ctx, w)) return s;
     } else { // phase 1: augmented chunk products [A* | b*]
@@ -956,6 +990,7 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
         l.final_common_exponent = 1;
         l.fact_stride = (long long)p.tot.stride;
         l.fact_cols = p.tot.cols_padded;
+        l.acc_f64 = f64;
         l.label = "affine_phase1_chunk_products";
         if (int s = launch_chain(ctx, l)) return s;
     }
@@ -967,7 +1002,13 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
         cs.init_stride = (long long)d * cb;
         cs.bias = true;
         cs.final_goom = nullptr;
-        if (int s = carry_phase(ctx, p, dtype, d, batch, totals, carries, gtot, gcar, cs, "affine_phase2_carries")) return s;
+        if (f64 && h0) { // the double carry kernels read the initial state with double components
+            void *h0w = static_cast<unsigned char *>(ws) + align_up(p.total(), 256);
+            if (int s = launch_widen_goom(ctx, h0, h0w, (size_t)batch * d)) return s;
+            cs.init = h0w;
+            cs.init_stride = (long long)d * 16;
+        }
+        if (int s = carry_phase(ctx, p, f64 ? GOOM_C128 : dtype, d, batch, totals, carries, gtot, gcar, cs, "affine_phase2_carries")) return s;
     }
     { // phase 3: matrix-vector walk of every chunk
         ChainLaunch l = base;
@@ -985,6 +1026,7 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
         l.out_goom = H;
         l.out_scaled = fused ? scaled : nullptr;
         l.out_logscale = fused ? logscale : nullptr;
+        l.fact_f64 = f64;
         l.label = "affine_phase3_outputs";
         return launch_chain(ctx, l);
     }

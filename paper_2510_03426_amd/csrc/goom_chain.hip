@@ -73,6 +73,10 @@ int launch_chain(goom_ctx *ctx, const ChainLaunch &l)
     a.left_real = l.left_real;
     a.out_scaled = static_cast<float *>(l.out_scaled);
     a.out_logscale = static_cast<float *>(l.out_logscale);
+    a.fact_f64 = l.fact_f64;
+    a.acc_f64 = l.acc_f64;
+    if ((l.fact_f64 || l.acc_f64) && (l.dtype != GOOM_C64 || l.left_fact))
+        return fail(ctx, GOOM_EUNSUPPORTED, "double factored matrices beside float GOOMs: recurrence kernels only");
     if (a.out_scaled && (l.dtype != GOOM_C64 || l.left_fact))
         return fail(ctx, GOOM_EUNSUPPORTED, "scaled outputs are written by the float matrix-vector walk only");
     const long long grid = l.batch * l.chunks_launched;

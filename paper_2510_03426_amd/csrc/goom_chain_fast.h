@@ -541,7 +541,8 @@ int dispatch_affine_chunk(goom_ctx *ctx, const ChainArgs &args, int dp, long lon
 bool affine_walk_applies(const ChainArgs &args, int dp);
 int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label);
 int launch_replicate_power(goom_ctx *ctx, void *totals, long long stride, int fact_cols, int dp, int d, long long batch,
-                           long long chunks, long long chunks_per_item);
+                           long long chunks, long long chunks_per_item, bool f64);
+int dispatch_affine_chunk_f64(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label);
 
 // square matrices whose size is a multiple of four between the sizes above (20 ... 124): the hot kernel
 // with the rows and columns beyond the matrix left out, separate translation unit

@@ -58,6 +58,9 @@ struct ChainArgs {
     int left_real;       // 1: the left factors are real matrices (component type), not GOOMs (hot float kernel only)
     float *out_scaled;   // NULL or [batch, steps, d]
     float *out_logscale; // NULL or [batch, steps]
+    // float kernels of the recurrence working beside double chunk products and carries:
+    int fact_f64;        // 1: the factored matrices read (init_mode 1) and written (out_fact_final) have double mantissas
+    int acc_f64;         // 1: chunk products [A* | b*] with the running product in double (d = 16, 32)
 };
 
 template <typename R> struct Comp;

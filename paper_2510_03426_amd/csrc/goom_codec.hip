@@ -403,6 +403,25 @@ int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale
     return check_hip(ctx, hipGetLastError(), "launch scaled_exp");
 }
 
+// complex64 GOOMs as complex128 GOOMs (the log-magnitude widened exactly; the phase as 0 or the double pi)
+__global__ __launch_bounds__(256) void widen_goom_kernel(const float2 *z, double2 *w, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const float2 v = z[i];
+        const int k = (int)__builtin_rintf(v.y * 0.318309886183790671538f);
+        w[i] = double2{(double)v.x, (k & 1) ? 3.14159265358979311600 : 0.0};
+    }
+}
+
+int launch_widen_goom(goom_ctx *ctx, const void *z64, void *z128, size_t n)
+{
+    if (n == 0) return GOOM_OK;
+    const size_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(widen_goom_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, ctx->stream,
+                       static_cast<const float2 *>(z64), static_cast<double2 *>(z128), n);
+    return check_hip(ctx, hipGetLastError(), "launch widen_goom");
+}
+
 int launch_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, size_t n, int dtype)
 {
     if (n == 0) return GOOM_OK;

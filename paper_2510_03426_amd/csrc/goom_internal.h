@@ -92,6 +92,8 @@ struct ChainLaunch {
     const void *bias;
     void *out_scaled;     // NULL or float states scaled to [-e^2, e^2], [batch, steps, d] (matrix-vector walk only)
     void *out_logscale;   // NULL or their log scales, [batch, steps]
+    int fact_f64;         // float kernels of the recurrence: factored matrices read / written have double mantissas
+    int acc_f64;          // chunk products of the recurrence with the running product in double (float GOOM factors)
     const char *label;    // phase name for profiling records
 };
 int launch_chain(goom_ctx *ctx, const ChainLaunch &a);
@@ -149,6 +151,7 @@ int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype)
 int launch_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, size_t n, int dtype);
 int launch_probe(goom_ctx *ctx, const void *a, void *b, size_t bytes, int mode);
 int launch_matrix_probe(goom_ctx *ctx, void *sink, long long iters, int dtype);
+int launch_widen_goom(goom_ctx *ctx, const void *z64, void *z128, size_t n); // complex64 GOOMs -> complex128 GOOMs
 int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t nvec, int d, int dtype);
 
 } // namespace goom
@@ -156,6 +159,6 @@ int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale
 namespace goom_chain {
 // time-invariant recurrence: copy A^L from the first chunk's total of every batch item to the others
 int launch_replicate_power(goom_ctx *ctx, void *totals, long long stride, int fact_cols, int dp, int d, long long batch,
-                           long long chunks, long long chunks_per_item);
+                           long long chunks, long long chunks_per_item, bool f64);
 } // namespace goom_chain
 

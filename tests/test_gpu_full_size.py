@@ -321,17 +321,9 @@ def test_config5_recurrence_full_size(G, oracle):
         # underestimates the sensitivity of an entry about one time in ten
         re, sg, kap, well = with_sensitivity(fn, [Az, bzh], np.float32, nprobe=3)
         got = host(hf[p])
-        # The parallel form multiplies each carried vector by a chunk product A*.  A float product of L
-        # matrices carries about sqrt(d L) 2^-24 = 3e-6 of error relative to its NORM, and A* is all but
-        # rank one, so that error reaches the new vector magnified by 1 / cos of the angle between the
-        # carried vector and the dominant input direction of A* (about sqrt(d) on average, more when
-        # the two are nearly orthogonal), and an entry then sees it magnified by its own cancellation
-        # factor.  The sequential oracle and its finite differences know nothing of this, so entries
-        # count as well conditioned here up to a cancellation factor of 2^7 rather than 2^9
-        # (3e-6 * sqrt(32) * 2^7 = 2e-3 relative, against a tolerance of 1e-4 * |log-magnitude|), and
-        # for the rare steps where the angle is far worse than average, five in a million of them may
-        # miss the tolerance, by less than a factor of three (measured: 2 of 2.1 million, by 1.13).
-        compare(got, re, sg, kap, name=f"config 5 sequence {p}", max_ill_fraction=0.05, well=well, kappa_limit=2.0 ** 7,
-                max_out_fraction=5e-6, hard_factor=3.0)
+        # chunk products and carries are held in double, so what reaches a state is the rounding of the last
+        # float walk alone, as in a sequential float evaluation: the stated tolerance holds on every entry
+        # the oracle marks well conditioned
+        compare(got, re, sg, kap, name=f"config 5 sequence {p}", max_ill_fraction=0.05, well=well)
         say(f"    |h_T| = exp({got.real[-1].max():.1f})")
     del az, bz, h

@@ -723,29 +723,29 @@ def test_signed_log_add(G, oracle, ctype):
     assert ulp.max() <= (1.0 if comp == np.float32 else 4.0)
 
 
-@pytest.mark.parametrize("T,d,batch,chunk,ctype", [(3000, 32, 3, 0, np.complex64), (500, 16, 2, 7, np.complex64), (100, 8, 2, 9, np.complex64),
-                                                   (400, 32, 1, 50, np.complex128), (64, 32, 2, 0, np.complex64)])
-def test_affine_scan_time_invariant(G, oracle, T, d, batch, chunk, ctype):
+# (cap: bound on the share of entries the oracle's probes call ill conditioned, about twice what the logs print.  A
+# slightly expansive constant matrix makes late states sensitive to the matrix itself: a perturbation of its
+# dominant eigenvalue by delta moves a state at step t by t * delta, the same way for every term of the sum.)
+@pytest.mark.parametrize("T,d,batch,chunk,ctype,gain,cap", [
+    (3000, 32, 3, 0, np.complex64, 1.02, 0.3), (2000, 32, 2, 0, np.complex64, 0.9, 0.05), (500, 16, 2, 7, np.complex64, 1.02, 0.07),
+    (100, 8, 2, 9, np.complex64, 1.02, 0.02), (400, 32, 1, 50, np.complex128, 1.02, 0.002), (64, 32, 2, 0, np.complex64, 1.02, 0.02)])
+def test_affine_scan_time_invariant(G, oracle, T, d, batch, chunk, ctype, gain, cap):
     # one matrix per sequence, applied at every step (the paper's state-space layer): against the oracle
     # fed the matrix repeated T times
     comp = np.float32 if ctype == np.complex64 else np.float64
-    A, b = si.recurrence_inputs(si.BASE_SEED + 57, batch, 1, d, gain=1.02)
+    A, b = si.recurrence_inputs(si.BASE_SEED + 57, batch, 1, d, gain=gain)
     A = A[:, 0].astype(comp)  # [batch, d, d]
     _, b = si.recurrence_inputs(si.BASE_SEED + 58, batch, T, d)
     Az, bz = oracle.to_goom(A), oracle.to_goom(b.astype(comp))
     Arep = np.ascontiguousarray(np.broadcast_to(Az[:, None], (batch, T, d, d)))
     say(f"time-invariant recurrence T={T} d={d} batch={batch} chunk={chunk} {np.dtype(ctype).name}")
-    fn = lambda a_, b_, h_: oracle.affine_scan(a_, b_, h0=h_, return_kappa=True)
+    # (the conditioning probe perturbs the one matrix that is the input, not T independent copies of it)
+    fn = lambda a_, b_, h_: oracle.affine_scan(np.ascontiguousarray(np.broadcast_to(a_[:, None], (batch, T, d, d))), b_, h0=h_, return_kappa=True)
     h0 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 59, 9, batch * d).reshape(batch, d).astype(comp))
     for start in (None, h0):
-        re, sg, kap, well = with_sensitivity(fn, [Arep, bz, start], comp)
+        re, sg, kap, well = with_sensitivity(fn, [Az, bz, start], comp)
         got = host(G.affine_scan(dev(Az), dev(bz), None if start is None else dev(start), chunk_len=chunk, time_invariant=True))
-        # a constant matrix of spectral radius near 1 neither amplifies nor forgets: the rounding of every
-        # step stays in the state for about 1 / (1 - radius) steps, and log-magnitudes stay small, so the
-        # absolute tolerance of 1e-3 applies throughout.  Float sums with a cancellation factor above 2^5
-        # are then not determined to 1e-3 (the purely sequential single-chunk walk shows the same), and
-        # the share of such entries is bounded instead.
-        compare(got, re, sg, kap, name=f"time-invariant T{T}d{d}", max_ill_fraction=0.12, well=well, kappa_limit=2.0 ** 5 if comp == np.float32 else None)
+        compare(got, re, sg, kap, name=f"time-invariant T{T}d{d}", max_ill_fraction=cap, well=well)
         # and it is the general entry point's result on the repeated matrix, to rounding
         ref = host(G.affine_scan(dev(Arep), dev(bz), None if start is None else dev(start), chunk_len=chunk))
         same = (ref.imag == got.imag) & (np.abs(ref.real - got.real) <= tolerance(ref.real.astype(np.float64), comp))
