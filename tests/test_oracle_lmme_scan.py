@@ -222,6 +222,31 @@ def test_scaled_oracle_agrees_with_definitional(oracle):
     assert np.array_equal(sg, ssg) and np.allclose(re, sre, rtol=1e-10, atol=1e-9)
 
 
+def test_scaled_oracle_on_the_first_16384_steps_of_the_long_chain(oracle):
+    # The second chain oracle (real mantissas with per-column power-of-two exponents) serves the full-size
+    # and the d > 128 parity tests, so it is held against the definitional signed log-sum-exp chain
+    # (Section 3.2, the LMME definition; Section 4.1, the chain) where that one can still be run: the first
+    # 16 384 steps of the long 64 x 64 chain (log-magnitudes reach 3.4e4, far past double range as reals),
+    # at 65 sampled prefixes, every entry; and on short chains of 128 x 128 and 256 x 256 matrices.
+    for d, T, every in [(64, 16384, 256), (128, 96, 8), (256, 24, 4)]:
+        Z = oracle.to_goom(si.normal_chain(si.BASE_SEED * 10 + 2, T, d))
+        samples = sorted(set(list(range(every - 1, T, every)) + [0, T - 1]))
+        a = oracle.ScanStream(d)
+        b = oracle.ScanStream(d, scaled=True)
+        re, sg, kap = a.advance(Z, sample_t=samples, return_kappa=True)
+        sre, ssg, skap = b.advance(Z, sample_t=samples, return_kappa=True)
+        ok = kap < 1e6
+        assert ok.mean() > 0.999
+        assert np.array_equal(sg[ok], ssg[ok])
+        # both walk the same chain in double: they differ by rounding that the cancellation factor magnifies,
+        # accumulated over the steps (a random walk: sqrt(T) units of 2^-53 on log-magnitudes of size |re|)
+        bound = 2.0 ** -52 * math.sqrt(T) * 8 * np.maximum(1.0, np.abs(re)) * np.maximum(1.0, kap)
+        assert np.all(np.abs(re - sre)[ok] <= bound[ok]), float((np.abs(re - sre) / bound)[ok].max())
+        assert np.allclose(kap[1:][ok[1:]], skap[1:][ok[1:]], rtol=1e-5)
+        if d == 64:
+            assert re.max() > 3.0e4  # about 2.07 per step
+
+
 # ------------------------------------------------------------------------------ affine
 
 def brute_affine(A, b, h0):
