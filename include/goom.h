@@ -225,9 +225,11 @@ size_t goom_reduce_real_workspace_bytes(int64_t T, int d, int m, int64_t batch, 
 
 typedef struct goom_reset_opts {
     int64_t chunk_len;    /* states are examined every chunk_len steps (t = chunk_len,
-                             2 chunk_len, ...); 0 = library default (32).  Longer
-                             chunks shorten the serial phase; in float arithmetic they also blur
-                             the split between nearly equal exponents */
+                             2 chunk_len, ...); 0 = library default (128).  Longer chunks shorten
+                             the serial phase; between two examined states the columns may close
+                             in on each other by a factor of about 1e5 (the spread of the
+                             exponents times chunk_len dt, as a power of e) before the
+                             factorisation, which runs in double, loses accuracy */
     int32_t policy;       /* GOOM_RESET_* */
     float cos_threshold;  /* used by GOOM_RESET_COLINEAR */
 } goom_reset_opts;
@@ -237,6 +239,9 @@ typedef struct goom_reset_opts {
  * prefix states at chunk boundaries: a selected state is replaced by the orthonormal
  * factor Q of its column-normalised real form (paper Section 4.2.1 (a)), and all later
  * states continue from Q.
+ * Both formats, d <= 64.  Chunk products, the prefixes at the chunk boundaries and the
+ * factorisations are computed in double for both formats; complex64 states are rounded once,
+ * when they are stored.
  * J: [batch, T, d, d]; S0: NULL or [batch, d, d]; states: [batch, T, d, d] (the state
  * after any reset at that step); reset_flags: NULL or [batch, T] bytes (1 where a reset
  * happened); growth: NULL or [batch, d] doubles: per column, the sum over resets of

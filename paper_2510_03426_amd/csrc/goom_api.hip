@@ -444,18 +444,22 @@ struct ResetPlan {
     size_t total() const { return tot_bytes + car_bytes + flag_bytes; }
 };
 
+// Chunk products, carries and the factorisations at the chunk boundaries are held in double for both formats
+// (for complex64 the chain kernels widen every load and round every stored state once): nearly colinear
+// columns are exactly what this variant exists for, and their small differences are what a float product loses.
 static ResetPlan plan_reset(long long T, int d, long long batch, int dtype, const goom_reset_opts *opts)
 {
     ResetPlan p;
-    p.L = (opts && opts->chunk_len > 0) ? opts->chunk_len : 32;
+    p.L = (opts && opts->chunk_len > 0) ? opts->chunk_len : 128;
     if (p.L > T) p.L = T;
     p.C = (T + p.L - 1) / p.L;
     p.dp = padded_dim(d);
-    p.tot = fact_layout(p.dp, d, dtype);
-    p.car = fact_layout(p.dp, d, dtype);
+    p.tot = fact_layout(p.dp, d, GOOM_C128);
+    p.car = fact_layout(p.dp, d, GOOM_C128);
     p.tot_bytes = (size_t)batch * p.C * p.tot.stride;
     p.car_bytes = (size_t)batch * (p.C + 1) * p.car.stride;
     p.flag_bytes = align_up((size_t)batch * p.C, 256);
+    (void)dtype;
     return p;
 }
 
@@ -466,7 +470,6 @@ static int run_reset(goom_ctx *ctx, const void *J, const void *S0, void *states,
     if (int s = check_common(ctx, dtype)) return s;
     if (!J) return fail(ctx, GOOM_EINVAL, "null data pointer");
     if (T <= 0 || batch <= 0 || d <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive (T=%lld d=%d batch=%lld)", T, d, batch);
-    if (dtype != GOOM_C64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan is built for GOOM_C64 only");
     if (d > 64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 64 (d=%d)", d);
     if (opts && opts->chunk_len < 0) return fail(ctx, GOOM_EINVAL, "negative chunk_len");
     const int policy = opts ? opts->policy : GOOM_RESET_ALWAYS;
@@ -484,7 +487,9 @@ static int run_reset(goom_ctx *ctx, const void *J, const void *S0, void *states,
 
     ChainLaunch base;
     std::memset(&base, 0, sizeof base);
-    base.dtype = dtype;
+    base.dp = p.dp;
+    base.dtype = GOOM_C128; // double running product
+    base.io_c64 = dtype == GOOM_C64 ? 1 : 0;
     base.n = d;
     base.d = d;
     base.m = d;
@@ -507,6 +512,7 @@ static int run_reset(goom_ctx *ctx, const void *J, const void *S0, void *states,
     }
     ResetLaunch r;
     std::memset(&r, 0, sizeof r);
+    r.dtype = dtype;
     r.totals = totals;
     r.tot_stride = (long long)p.tot.stride;
     r.tot_cols = p.tot.cols_padded;
@@ -1048,7 +1054,7 @@ int goom_affine_scan_scaled(goom_ctx *ctx, const void *A, const void *bias, cons
 
 size_t goom_scan_reset_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts)
 {
-    if (T <= 0 || d <= 0 || batch <= 0 || d > 64 || dtype != GOOM_C64) return 0;
+    if (T <= 0 || d <= 0 || batch <= 0 || d > 64 || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
     const ResetPlan p = plan_reset(T, d, batch, dtype, opts);
     return p.total();
 }

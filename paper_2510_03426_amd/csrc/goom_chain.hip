@@ -82,6 +82,11 @@ int launch_chain(goom_ctx *ctx, const ChainLaunch &l)
     const long long grid = l.batch * l.chunks_launched;
     if (l.left_real && (l.dtype != GOOM_C64 || l.left_fact))
         return fail(ctx, GOOM_EUNSUPPORTED, "real left factors are read by the hot float kernel only");
+    if (l.io_c64) {
+        if (l.dtype != GOOM_C128 || l.left_fact || l.left_real || l.out_scaled)
+            return fail(ctx, GOOM_EUNSUPPORTED, "complex64 data with a double running product: GOOM left factors only");
+        return goom_chain::dispatch_f64_goom_io32(ctx, a, dp, nw, grid, l.label);
+    }
     if (l.dtype == GOOM_C64)
         return l.left_fact ? goom_chain::dispatch_f32_fact(ctx, a, dp, nw, grid, l.label) : goom_chain::dispatch_f32_goom(ctx, a, dp, nw, grid, l.label);
     return l.left_fact ? goom_chain::dispatch_f64_fact(ctx, a, dp, nw, grid, l.label) : goom_chain::dispatch_f64_goom(ctx, a, dp, nw, grid, l.label);

@@ -318,7 +318,10 @@ constexpr int waves_per_simd(int comp_bytes, int dp, int nw)
 // FAST: the factor fills the padded tile exactly (n = d = DP), the state has whole
 // 16-column slabs and there is no bias column, so every bounds test and the bias path
 // compile away and the step is straight-line code.
-template <typename R, int DP, int NW, int LEFT_FACT, bool FAST>
+// IO: component type of the GOOM arrays in memory (left factors, initial state, bias, outputs).  It differs
+// from R in one combination only, IO = float with R = double: complex64 data walked with a double running
+// product (every load widened, every output rounded once when it is stored).
+template <typename R, int DP, int NW, int LEFT_FACT, bool FAST, typename IO = R>
 __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void chain_kernel(ChainArgs a)
 {
     constexpr int KT = DP / 16;
@@ -387,9 +390,9 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                 it[q].re1 = v1 ? mp[1] : (R)0;
                 it[q].im0 = it[q].im1 = (R)0;
             } else {
-                const R *gp = reinterpret_cast<const R *>(src) + (size_t)(row * ld + cj) * 2;
+                const IO *gp = reinterpret_cast<const IO *>(src) + (size_t)(row * ld + cj) * 2;
                 if (FAST || (v1 && vec_ok)) {
-                    if (sizeof(R) == 4) {
+                    if (sizeof(IO) == 4) {
                         const f4 w = *reinterpret_cast<const f4 *>(gp);
                         it[q].re0 = w[0]; it[q].im0 = w[1]; it[q].re1 = w[2]; it[q].im1 = w[3];
                     } else {
@@ -476,7 +479,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
         ecol = slab_active ? ep[col] : 0.0;
     } else {
         // GOOM initial state [d, m]: column shift e = ceil(max_i log2|x_ik|), W = +-2^(log2|x| - e)
-        const R *gp = reinterpret_cast<const R *>(a.init + item * a.init_stride);
+        const IO *gp = reinterpret_cast<const IO *>(a.init + item * a.init_stride);
         R cmax = kNegInf;
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
@@ -625,7 +628,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
             bneg = false;
             if (i >= n_rows) return;
             if (a.bias_mode == 1) {
-                const R *bp = reinterpret_cast<const R *>(a.bias) + ((size_t)(item * a.steps + t0 + t) * n_rows + i) * 2;
+                const IO *bp = reinterpret_cast<const IO *>(a.bias) + ((size_t)(item * a.steps + t0 + t) * n_rows + i) * 2;
                 R br = bp[0];
                 if (br > kNegInf) blog = (double)br * kLog2e - ecol;
                 bneg = Comp<R>::is_negative(bp[1]);
@@ -672,12 +675,12 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
 
         const bool want_out = a.out_goom && slab_active && (FAST || col < m) && (!a.out_goom_last_only || t == len - 1);
         // (in FAST kernels every term above is wave-uniform)
-        R *outp = nullptr;
+        IO *outp = nullptr;
         if (want_out) {
             long long o_idx = a.out_goom_last_only ? chain_global : (item * a.steps + t0 + t);
             // (FAST: the sizes are the template's, so the offsets of a lane's entries are constants and
             // need no registers across the loop)
-            outp = reinterpret_cast<R *>(a.out_goom) + (FAST ? (size_t)o_idx * (DP * 16 * NW) : (size_t)o_idx * n_rows * m) * 2;
+            outp = reinterpret_cast<IO *>(a.out_goom) + (FAST ? (size_t)o_idx * (DP * 16 * NW) : (size_t)o_idx * n_rows * m) * 2;
         }
 
         // (the row stride is made opaque here so that the offsets of a lane's entries are not kept in
@@ -692,7 +695,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
         if (FAST) {
             if (want_out) { // wave-uniform: one branch around all of this step's stores
                 // the lane's first entry; the others lie at constant distances from it (row_of is linear)
-                R *ob = outp + (Comp<R>::row_of(g, 0) * (16 * NW) + col) * 2;
+                IO *ob = outp + (Comp<R>::row_of(g, 0) * (16 * NW) + col) * 2;
 #pragma unroll
                 for (int mt = 0; mt < KT; ++mt) {
                     const vec4 nv = *reinterpret_cast<const vec4 *>(&nsh[16 * mt + 4 * g]);
@@ -700,9 +703,9 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                     for (int v = 0; v < 4; ++v) {
                         const R x = acc[mt][v];
                         const R re = Comp<R>::out_re(x, nv[v], ecol);
-                        const R im = x < (R)0 ? Comp<R>::pi() : (R)0;
-                        R *o = ob + ((16 * mt + Comp<R>::row_of(0, v)) * (16 * NW)) * 2;
-                        if (sizeof(R) == 4) {
+                        const IO im = x < (R)0 ? Comp<IO>::pi() : (IO)0;
+                        IO *o = ob + ((16 * mt + Comp<R>::row_of(0, v)) * (16 * NW)) * 2;
+                        if (sizeof(IO) == 4) {
                             *reinterpret_cast<float2 *>(o) = float2{(float)re, (float)im};
                         } else {
                             *reinterpret_cast<double2 *>(o) = double2{(double)re, (double)im};
@@ -728,9 +731,9 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                     const R x = acc[mt][v];
                     if (want_out && i < n_rows) {
                         const R re = Comp<R>::out_re(x, nv[v], ecol);
-                        const R im = x < (R)0 ? Comp<R>::pi() : (R)0;
-                        R *o = outp + (size_t)(i * mo + col) * 2;
-                        if (sizeof(R) == 4) {
+                        const IO im = x < (R)0 ? Comp<IO>::pi() : (IO)0;
+                        IO *o = outp + (size_t)(i * mo + col) * 2;
+                        if (sizeof(IO) == 4) {
                             *reinterpret_cast<float2 *>(o) = float2{(float)re, (float)im};
                         } else {
                             *reinterpret_cast<double2 *>(o) = double2{(double)re, (double)im};
@@ -756,9 +759,9 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                     const R xs = xa + (bneg ? -xb : xb);
                     if (want_out && i < n_rows) {
                         const R re = Comp<R>::out_re(xs, cms, ecol);
-                        const R im = xs < (R)0 ? Comp<R>::pi() : (R)0;
-                        R *o = outp + (size_t)(i * mo + col) * 2;
-                        o[0] = re;
+                        const IO im = xs < (R)0 ? Comp<IO>::pi() : (IO)0;
+                        IO *o = outp + (size_t)(i * mo + col) * 2;
+                        o[0] = (IO)re;
                         o[1] = im;
                     }
                     st[mt][v] = xs;
@@ -787,13 +790,13 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
     if (a.out_fact_final) store_fact(a.out_fact_final + chain_global * a.fact_stride, a.final_common_exponent != 0);
 }
 
-template <typename R, int DP, int NW, int LEFT_FACT, bool FAST> int launch_one(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
+template <typename R, int DP, int NW, int LEFT_FACT, bool FAST, typename IO = R> int launch_one(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
 {
     constexpr int LDA = DP + Comp<R>::kPad;
     const size_t buf = (size_t)DP * LDA * sizeof(R) + (size_t)DP * sizeof(double);
     const int nbuf = (2 * buf + 64 <= 160 * 1024) ? 2 : 1;
     size_t lds = nbuf * buf + 64;
-    auto kern = chain_kernel<R, DP, NW, LEFT_FACT, FAST>;
+    auto kern = chain_kernel<R, DP, NW, LEFT_FACT, FAST, IO>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return goom::check_hip(ctx, e, "hipFuncSetAttribute(chain_kernel)");
@@ -806,13 +809,13 @@ template <typename R, int DP, int NW, int LEFT_FACT, bool FAST> int launch_one(g
     return goom::check_hip(ctx, hipGetLastError(), "launch chain_kernel");
 }
 
-template <typename R, int LEFT_FACT> int dispatch(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label)
+template <typename R, int LEFT_FACT, typename IO = R> int dispatch(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label)
 {
     const bool fast = args.n == dp && args.d == dp && args.m == 16 * nw && args.bias_mode == 0;
 #define GOOM_CASE(DPV, NWV)                                                                           \
     if (dp == DPV && nw == NWV)                                                                       \
-        return fast ? launch_one<R, DPV, NWV, LEFT_FACT, true>(ctx, args, grid, label)                \
-                    : launch_one<R, DPV, NWV, LEFT_FACT, false>(ctx, args, grid, label);
+        return fast ? launch_one<R, DPV, NWV, LEFT_FACT, true, IO>(ctx, args, grid, label)            \
+                    : launch_one<R, DPV, NWV, LEFT_FACT, false, IO>(ctx, args, grid, label);
     GOOM_CASE(16, 1)
     GOOM_CASE(16, 2)
     GOOM_CASE(32, 1)
@@ -833,5 +836,7 @@ int dispatch_f32_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long
 int dispatch_f32_fact(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label);
 int dispatch_f64_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label);
 int dispatch_f64_fact(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label);
+// double running product over complex64 GOOMs (left factors, initial state, bias, outputs)
+int dispatch_f64_goom_io32(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long long grid, const char *label);
 
 } // namespace goom_chain

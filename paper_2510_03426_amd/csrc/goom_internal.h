@@ -92,6 +92,8 @@ struct ChainLaunch {
     const void *bias;
     void *out_scaled;     // NULL or float states scaled to [-e^2, e^2], [batch, steps, d] (matrix-vector walk only)
     void *out_logscale;   // NULL or their log scales, [batch, steps]
+    int io_c64;           // with dtype GOOM_C128: the GOOM arrays (left, init, bias, outputs) are complex64; the running
+                          // product and every factored matrix are double
     int fact_f64;         // float kernels of the recurrence: factored matrices read / written have double mantissas
     int acc_f64;          // chunk products of the recurrence with the running product in double (float GOOM factors)
     const char *label;    // phase name for profiling records
@@ -99,6 +101,7 @@ struct ChainLaunch {
 int launch_chain(goom_ctx *ctx, const ChainLaunch &a);
 
 struct ResetLaunch {
+    int dtype;            // of the GOOM arrays (s0, post_states); totals and carries always have double mantissas
     const void *totals;   // factored chunk products [batch][C]
     long long tot_stride;
     int tot_cols;

@@ -37,7 +37,7 @@ struct ResetArgs {
     unsigned char *carries;      // [batch][C + 1] factored prefixes entering each chunk (and the final state), DP x car_cols
     long long car_stride;
     int car_cols;
-    const float *s0;             // NULL or GOOM initial state [batch][d][d]
+    const void *s0;              // NULL or GOOM initial state [batch][d][d] (complex64 or complex128)
     unsigned char *chunk_flags;  // [batch][C]: 1 where the state at the end of chunk c was reset
     double *growth;              // NULL or [batch][d]
     double growth_scale;         // 1, or 1 / (dt T) to return exponents
@@ -93,40 +93,6 @@ template <int DP> struct Wave {
     double diag[DP];      // diagonal of the Gram matrix
     float qpanel[DP / 16][DP * 20]; // finished panels of Q, [row][column within the panel], rows padded to 20
 };
-
-// G = Z^T Z in double; G[nt][mt][v] = entry (row 16 mt + 4 v + g, column 16 nt + c)
-template <int DP> __device__ void gram(const f4 (&Z)[DP / 16][DP / 16], d4 (&G)[DP / 16][DP / 16])
-{
-    constexpr int KT = DP / 16;
-#pragma unroll
-    for (int nt = 0; nt < KT; ++nt)
-#pragma unroll
-        for (int mt = 0; mt < KT; ++mt) {
-            d4 acc = {0., 0., 0., 0.};
-#pragma unroll
-            for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64((double)Z[mt][kt][v], (double)Z[nt][kt][v], acc, 0, 0, 0);
-            G[nt][mt] = acc;
-        }
-}
-
-// the diagonal of G into s.diag (entry j at position j)
-template <int DP> __device__ void diagonal_to_lds(const d4 (&G)[DP / 16][DP / 16], Wave<DP> &s, int g, int c)
-{
-    constexpr int KT = DP / 16;
-#pragma unroll
-    for (int nt = 0; nt < KT; ++nt) {
-        // G[j][j] for column j = 16 nt + c: row part c = 4 v + g', so it sits in lane (c % 4, c), register c / 4
-        double dsel = G[nt][nt][0];
-        dsel = (c >> 2) == 1 ? G[nt][nt][1] : dsel;
-        dsel = (c >> 2) == 2 ? G[nt][nt][2] : dsel;
-        dsel = (c >> 2) == 3 ? G[nt][nt][3] : dsel;
-        if (g == (c & 3)) s.diag[16 * nt + c] = dsel;
-    }
-    wave_sync();
-}
 
 // The factorisation runs panel by panel (16 columns at a time), in square-root-free form: a step
 // subtracts (G_kj / p_k) times row / column k from every later one of the panel, p_k = G_kk being the
@@ -250,21 +216,187 @@ template <int DP> __device__ float qr_panels(f4 (&Z)[DP / 16][DP / 16], double (
     return read_lane(worst, 0); // the same in every lane; this tells the compiler so
 }
 
-template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(ResetArgs a)
+// ---------------------------------------------------------------------------------------------------
+// The carry kernel keeps everything in double: the chunk products arrive in double, Z = T Y and every step
+// of the factorisation run on the double-precision matrix instruction and the double vector ALU.  The
+// 16 x 16 x 4 double instruction leaves rows 4 v + g of column c in register v of lane (g, c), takes
+// A[row c][k = g] and B[k = g][column c] from lane (g, c); so a matrix held as [nt][mt] tiles in that result
+// layout is, register for register, a B operand whose contraction index runs 4 v + g, and an A operand of
+// its transpose.  Whatever is read from LDS as a four-vector therefore stores index 4 v + g at position
+// 4 g + v (perm16 below).
+__device__ inline int perm16(int j) { return (j & ~15) | ((j & 3) << 2) | ((j >> 2) & 3); }
+
+template <int DP> struct WaveD {
+    static constexpr int LDT = DP + 2;  // row stride of the chunk product (doubles)
+    static constexpr int LDQ = 18;      // row stride of a finished panel
+    double tile[DP * LDT]; // chunk product, rows in order, columns in perm16 order
+    double rrow[2][16];   // row k of the panel's Gram matrix at step k, entry j at position j
+    double rperm[2][16];  // the same in perm16 order
+    double qcol[2][DP];   // column k of the panel at step k, rows in perm16 order
+    double diag[DP];      // diagonal of the Gram matrix (selection by cosines)
+    double qpanel[DP / 16 > 1 ? DP / 16 - 1 : 1][DP * LDQ]; // finished panels of Q: [row][column within the panel, perm16 order]
+};
+
+__device__ inline d4 mfma8(double x, double y, d4 acc) { return __builtin_amdgcn_mfma_f64_16x16x4f64(x, y, acc, 0, 0, 0); }
+
+__device__ inline double read_lane_d(double v, int lane)
+{
+    const unsigned long long u = __builtin_bit_cast(unsigned long long, v);
+    const int lo = __builtin_amdgcn_readlane((int)(u & 0xffffffffull), lane);
+    const int hi = __builtin_amdgcn_readlane((int)(u >> 32), lane);
+    return __builtin_bit_cast(double, ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
+}
+
+// 1 / x and 1 / sqrt(x) to double precision from the float hardware approximations (x within float range)
+__device__ inline double rcp_d(double x)
+{
+    double r = (double)__builtin_amdgcn_rcpf((float)x);
+    r = r * (2.0 - x * r);
+    return r * (2.0 - x * r);
+}
+__device__ inline double rsqrt_d(double x)
+{
+    double r = (double)__builtin_amdgcn_rsqf((float)x);
+    r = r * (1.5 - 0.5 * x * r * r);
+    return r * (1.5 - 0.5 * x * r * r);
+}
+
+// elimination of one panel (see eliminate_panel above), columns in double
+template <int DP> __device__ void eliminate_panel_d(d4 &G, d4 (&Zp)[DP / 16], double &piv, WaveD<DP> &s, int g, int c)
 {
     constexpr int KT = DP / 16;
-    constexpr int LDT = DP + 4;
-    constexpr int TQ = DP * DP / 4 / 64; // 16-byte pieces of the chunk product per lane
-    __shared__ __align__(16) Wave<DP> s;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const int gk = k % 4, vk = k / 4;
+        const int buf = k & 1;
+        double *rrow = s.rrow[buf];
+        double *rperm = s.rperm[buf];
+        double *qcol = s.qcol[buf];
+        if (g == gk) {
+            const double r = c > k ? G[vk] : 0.0;
+            rrow[c] = r;
+            rperm[((c & 3) << 2) | (c >> 2)] = r;
+        }
+        if (c == k) {
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) *reinterpret_cast<d4 *>(&qcol[16 * mt + 4 * g]) = Zp[mt];
+        }
+        const double pivot = read_lane_d(G[vk], 16 * gk + k);
+        if (c == k) piv = pivot;
+        const double inv = pivot > 1.0e-280 ? rcp_d(pivot) : 0.0;
+        wave_sync();
+        const double tj = rrow[c] * inv;
+        const d4 ri = *reinterpret_cast<const d4 *>(&rperm[4 * g]);
+        G -= ri * tj;
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) {
+            const d4 zk = *reinterpret_cast<const d4 *>(&qcol[16 * mt + 4 * g]);
+            Zp[mt] -= zk * tj;
+        }
+    }
+    wave_sync();
+}
+
+// QR of Z in place (Z <- Q), panel by panel; piv[nt] = squared diagonal of R for column 16 nt + c.  Returns the
+// largest ratio (squared column norm) / pivot, a measure of cond(Z)^2.  Before the factorisation every column
+// is scaled by a power of two to a largest entry near 1 (cexp receives the exponents), so that pivots stay
+// inside the range of the float reciprocal estimates.
+template <int DP> __device__ double qr_panels_d(d4 (&Z)[DP / 16][DP / 16], double (&piv)[DP / 16], double (&cexp)[DP / 16], WaveD<DP> &s, int g, int c)
+{
+    constexpr int KT = DP / 16;
+    constexpr int LDQ = WaveD<DP>::LDQ;
+    double norm2[KT];
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) {
+        double mx = 0.0;
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) mx = fmax(mx, fabs(Z[nt][mt][v]));
+        mx = fmax(mx, __shfl_xor(mx, 16, 64));
+        mx = fmax(mx, __shfl_xor(mx, 32, 64));
+        int ex = 0;
+        if (mx > 0.0) (void)frexp(mx, &ex);
+        cexp[nt] = (double)ex;
+        double a = 0.0;
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                Z[nt][mt][v] = ldexp(Z[nt][mt][v], -ex);
+                a = fma(Z[nt][mt][v], Z[nt][mt][v], a);
+            }
+        a += __shfl_xor(a, 16, 64);
+        a += __shfl_xor(a, 32, 64);
+        norm2[nt] = a;
+    }
+#pragma unroll
+    for (int p = 0; p < KT; ++p) {
+        // orthogonal to the finished panels (twice: one projection leaves rounding-level remainders of the
+        // panel's norm behind, which the panel's own, much smaller, remainder would magnify)
+#pragma unroll
+        for (int rep = 0; rep < (p > 0 ? 2 : 0); ++rep)
+#pragma unroll
+            for (int q = 0; q < p; ++q) {
+                d4 R = {0., 0., 0., 0.};
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) R = mfma8(Z[q][kt][v], Z[p][kt][v], R);
+                R = -R;
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt) {
+                    const d4 av = *reinterpret_cast<const d4 *>(&s.qpanel[q][(16 * mt + c) * LDQ + 4 * g]);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) Z[p][mt] = mfma8(av[v], R[v], Z[p][mt]);
+                }
+            }
+        d4 G = {0., 0., 0., 0.};
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) G = mfma8(Z[p][kt][v], Z[p][kt][v], G);
+        piv[p] = 1.0;
+        eliminate_panel_d<DP>(G, Z[p], piv[p], s, g, c);
+        const double sc = piv[p] > 1.0e-280 ? rsqrt_d(piv[p]) : 0.0;
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) Z[p][mt] *= sc;
+        if (p + 1 < KT) {
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) s.qpanel[p][(16 * mt + 4 * v + g) * LDQ + (((c & 3) << 2) | (c >> 2))] = Z[p][mt][v];
+            wave_sync();
+        }
+    }
+    double worst = 1.0;
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) {
+        const double ratio = piv[nt] > 1.0e-280 ? norm2[nt] * rcp_d(piv[nt]) : 1.0;
+        worst = fmax(worst, ratio);
+    }
+#pragma unroll
+    for (int sft = 1; sft < 16; sft <<= 1) worst = fmax(worst, __shfl_xor(worst, sft, 64));
+    return read_lane_d(worst, 0);
+}
+
+// IO: component type of the GOOM initial state (float for complex64, double for complex128)
+template <int DP, typename IO> __global__ __launch_bounds__(64) void reset_carry_kernel(ResetArgs a)
+{
+    constexpr int KT = DP / 16;
+    constexpr int LDT = WaveD<DP>::LDT;
+    constexpr int TQ = DP * DP / 4 / 64; // 32-byte pieces (four doubles) of the chunk product per lane
+    constexpr bool PREFETCH = DP <= 32;  // the next chunk product waits in registers during the factorisation
+    __shared__ __align__(32) WaveD<DP> s;
     const int lane = threadIdx.x;
     const int g = lane >> 4, c = lane & 15;
     const int d = a.d;
     const long long b = blockIdx.x;
-    const size_t tot_mant = (size_t)DP * a.tot_cols * sizeof(float);
-    const size_t car_mant = (size_t)DP * a.car_cols * sizeof(float);
+    const size_t tot_mant = (size_t)DP * a.tot_cols * sizeof(double);
+    const size_t car_mant = (size_t)DP * a.car_cols * sizeof(double);
 
-    f4 Y[KT][KT];    // state, columns scaled by 2^yexp
-    double yexp[KT]; // exponent of column 16 nt + c
+    d4 Y[KT][KT];    // state: Y[nt][mt][v] = entry (row 16 mt + 4 v + g, column 16 nt + c), columns scaled by 2^yexp
+    double yexp[KT];
     double pprod[KT], pexp[KT]; // product of all pivots so far = pprod 2^pexp (column exponents counted twice: pivots are squares)
 #pragma unroll
     for (int nt = 0; nt < KT; ++nt) {
@@ -272,34 +404,34 @@ template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(Reset
         pprod[nt] = 1.0;
         pexp[nt] = 0.0;
     }
-    // ---- initial state: identity or the given GOOM matrix; rows and columns past d carry an
-    // identity block, which stays orthogonal to everything and never reaches the outputs
+    // ---- initial state: identity or the given GOOM matrix; rows and columns past d carry an identity block,
+    // which stays orthogonal to everything and never reaches the outputs
 #pragma unroll
     for (int nt = 0; nt < KT; ++nt)
 #pragma unroll
         for (int mt = 0; mt < KT; ++mt)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) Y[nt][mt][v] = (16 * mt + 4 * g + v == 16 * nt + c) ? 1.0f : 0.0f;
+            for (int v = 0; v < 4; ++v) Y[nt][mt][v] = (16 * mt + 4 * v + g == 16 * nt + c) ? 1.0 : 0.0;
     if (a.s0) {
-        const float *gp = a.s0 + (size_t)b * d * d * 2;
+        const IO *gp = reinterpret_cast<const IO *>(a.s0) + (size_t)b * d * d * 2;
 #pragma unroll
         for (int nt = 0; nt < KT; ++nt) {
             const int col = 16 * nt + c;
             if (col < d) {
-                float cmax = -__builtin_huge_valf();
-                for (int i = 0; i < d; ++i) cmax = fmaxf(cmax, gp[((size_t)i * d + col) * 2]);
-                yexp[nt] = cmax > -__builtin_huge_valf() ? ceil((double)cmax * kLog2e) : 0.0;
+                double cmax = -__builtin_huge_val();
+                for (int i = 0; i < d; ++i) cmax = fmax(cmax, (double)gp[((size_t)i * d + col) * 2]);
+                yexp[nt] = cmax > -__builtin_huge_val() ? ceil(cmax * kLog2e) : 0.0;
 #pragma unroll
                 for (int mt = 0; mt < KT; ++mt)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const int row = 16 * mt + 4 * g + v;
-                        float val = 0.0f;
+                        const int row = 16 * mt + 4 * v + g;
+                        double val = 0.0;
                         if (row < d) {
-                            const float *e = gp + ((size_t)row * d + col) * 2;
+                            const IO *e = gp + ((size_t)row * d + col) * 2;
                             const double t = (double)e[0] * kLog2e - yexp[nt];
-                            val = t > -300.0 ? (float)exp2(t) : 0.0f;
-                            if ((int)rintf(e[1] * 0.318309886183790671538f) & 1) val = -val;
+                            val = t > -1000.0 ? exp2(t) : 0.0;
+                            if ((int)rint((double)e[1] * 0.318309886183790671538) & 1) val = -val;
                         }
                         Y[nt][mt][v] = val;
                     }
@@ -309,7 +441,7 @@ template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(Reset
 
     auto store_carry = [&](long long cc) {
         unsigned char *dst = a.carries + (b * (a.C + 1) + cc) * a.car_stride;
-        float *mp = reinterpret_cast<float *>(dst);
+        double *mp = reinterpret_cast<double *>(dst);
         double *ep = reinterpret_cast<double *>(dst + car_mant);
 #pragma unroll
         for (int nt = 0; nt < KT; ++nt) {
@@ -319,104 +451,101 @@ template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(Reset
                 for (int mt = 0; mt < KT; ++mt)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const int row = 16 * mt + 4 * g + v;
-                        mp[(size_t)row * a.car_cols + col] = (row < d && col < d) ? Y[nt][mt][v] : 0.0f;
+                        const int row = 16 * mt + 4 * v + g;
+                        mp[(size_t)row * a.car_cols + col] = (row < d && col < d) ? Y[nt][mt][v] : 0.0;
                     }
                 if (g == 0) ep[col] = col < d ? yexp[nt] : 0.0;
             }
         }
     };
 
-    // chunk product c: mantissas as 16-byte pieces (row = piece / (DP / 4)), and its common exponent
-    auto load_total = [&](long long cc, f4 (&tq)[TQ], double &tex) {
-        const unsigned char *tp = a.totals + (b * a.C + cc) * a.tot_stride;
-        const float *tm = reinterpret_cast<const float *>(tp);
-        tex = *reinterpret_cast<const double *>(tp + tot_mant);
-#pragma unroll
-        for (int q = 0; q < TQ; ++q) {
-            const int piece = lane + 64 * q;
-            const int row = piece / (DP / 4), c4 = 4 * (piece % (DP / 4));
-            tq[q] = *reinterpret_cast<const f4 *>(tm + (size_t)row * a.tot_cols + c4);
-        }
+    // chunk product cc: mantissas as pieces of four doubles (row = piece / (DP / 4)), and its common exponent
+    auto total_ptr = [&](long long cc) { return a.totals + (b * a.C + cc) * a.tot_stride; };
+    auto load_piece = [&](const unsigned char *tp, int q) {
+        const int piece = lane + 64 * q;
+        const int row = piece / (DP / 4), c4 = 4 * (piece % (DP / 4));
+        return *reinterpret_cast<const d4 *>(reinterpret_cast<const double *>(tp) + (size_t)row * a.tot_cols + c4);
     };
-    auto tile_from = [&](const f4 (&tq)[TQ]) {
+    auto tile_piece = [&](double *tile, int q, d4 val) {
+        const int piece = lane + 64 * q;
+        const int row = piece / (DP / 4), c4 = 4 * (piece % (DP / 4));
+        const int p4 = (c4 & ~15) | ((c4 >> 2) & 3);
 #pragma unroll
-        for (int q = 0; q < TQ; ++q) {
-            const int piece = lane + 64 * q;
-            const int row = piece / (DP / 4), c4 = 4 * (piece % (DP / 4));
-            f4 val = tq[q];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) // identity block past d
-                if (row >= d || c4 + e >= d) val[e] = (c4 + e == row) ? 1.0f : 0.0f;
-            *reinterpret_cast<f4 *>(&s.tile[row * LDT + c4]) = val;
+        for (int e = 0; e < 4; ++e) {
+            double x = val[e];
+            if (row >= d || c4 + e >= d) x = (c4 + e == row) ? 1.0 : 0.0; // identity block past d
+            tile[row * LDT + p4 + 4 * e] = x;
         }
     };
 
-    // squared cosines between columns from the Gram matrix: any pair above the threshold?
-    auto near_colinear = [&](const d4 (&G)[KT][KT]) {
-        diagonal_to_lds<DP>(G, s, g, c);
-        bool hit = false;
-        const double thr2 = (double)a.cos_threshold * (double)a.cos_threshold;
+    // QR of Z in place (Z <- Q).  The growth it removes, ln R_kk + ln 2 * (exponent of column k), is kept as a
+    // running product of pivots (mantissa and binary exponent apart) plus a sum of exponents, so that no logarithm
+    // is taken inside the chain of chunks.
+    auto qr_in_place = [&](d4 (&Z)[KT][KT], const double (&colexp)[KT]) {
+        double piv[KT], piv2[KT], ce[KT], ce2[KT];
+        const double amp = qr_panels_d<DP>(Z, piv, ce, s, g, c);
 #pragma unroll
         for (int nt = 0; nt < KT; ++nt) {
-            const double dc = s.diag[16 * nt + c];
-#pragma unroll
-            for (int mt = 0; mt < KT; ++mt)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int row = 16 * mt + 4 * v + g, col = 16 * nt + c;
-                    const double dr = s.diag[row];
-                    const double x = G[nt][mt][v];
-                    if (row < col && col < d && x * x > thr2 * dr * dc) hit = true;
-                }
+            piv2[nt] = 1.0;
+            ce2[nt] = 0.0;
         }
-        wave_sync();
-        return __builtin_amdgcn_ballot_w64(hit) != 0;
-    };
-
-    // QR of Z in place (Z <- Q).  The growth it removes, ln R_kk + ln 2 * colexp_k per column, is
-    // kept as a running product of pivots (mantissa and binary exponent apart) plus a sum of
-    // exponents, so that no logarithm is taken inside the chain of chunks.
-    auto qr_in_place = [&](f4 (&Z)[KT][KT], const double (&colexp)[KT]) {
-        double piv[KT], piv2[KT];
-        const float amp = qr_panels<DP>(Z, piv, s, g, c);
-#pragma unroll
-        for (int nt = 0; nt < KT; ++nt) piv2[nt] = 1.0;
-        if (amp > 65536.0f) (void)qr_panels<DP>(Z, piv2, s, g, c); // float column updates lose about sqrt(amp) 2^-24 of orthogonality: once more
+        // The factor Q comes out with errors of about amp 2^-53 relative to its columns' norms (amp: the squared
+        // condition number).  For complex64 states, which are rounded to float, that is repaired by a second
+        // factorisation from amp = 1e10 on; complex128 states take the second factorisation from 1e3 on.
+        if (amp > (sizeof(IO) == 4 ? 1.0e10 : 1.0e3)) (void)qr_panels_d<DP>(Z, piv2, ce2, s, g, c);
 #pragma unroll
         for (int nt = 0; nt < KT; ++nt)
-            if (piv[nt] > 1.0e-30 && piv2[nt] > 1.0e-30) {
+            if (piv[nt] > 1.0e-280 && piv2[nt] > 1.0e-280) {
                 int e;
                 pprod[nt] = frexp(pprod[nt] * piv[nt] * piv2[nt], &e);
-                pexp[nt] += 2.0 * colexp[nt] + (double)e;
+                pexp[nt] += 2.0 * (colexp[nt] + ce[nt] + ce2[nt]) + (double)e;
             }
     };
 
-    f4 tq[TQ];
+    d4 tq[PREFETCH ? TQ : 1];
     double tex_next = 0.0;
-    if (a.C > 0) load_total(0, tq, tex_next);
+    if (PREFETCH && a.C > 0) {
+        const unsigned char *tp = total_ptr(0);
+        tex_next = *reinterpret_cast<const double *>(tp + tot_mant);
+#pragma unroll
+        for (int q = 0; q < TQ; ++q) tq[q] = load_piece(tp, q);
+    }
 
     for (long long cc = 0; cc < a.C; ++cc) {
         store_carry(cc);
-        const double tex = tex_next;
-        tile_from(tq);
+        double tex = tex_next;
+        double *tile = s.tile;
+        if (PREFETCH) {
+#pragma unroll
+            for (int q = 0; q < TQ; ++q) tile_piece(tile, q, tq[q]);
+        } else { // (64-wide: the registers are taken by the state; the chunk product goes straight to LDS)
+            const unsigned char *tp = total_ptr(cc);
+            tex = *reinterpret_cast<const double *>(tp + tot_mant);
+#pragma unroll 4
+            for (int q = 0; q < TQ; ++q) tile_piece(tile, q, load_piece(tp, q));
+        }
         wave_sync();
-        if (cc + 1 < a.C) load_total(cc + 1, tq, tex_next);
+        if (PREFETCH && cc + 1 < a.C) {
+            const unsigned char *tp = total_ptr(cc + 1);
+            tex_next = *reinterpret_cast<const double *>(tp + tot_mant);
+#pragma unroll
+            for (int q = 0; q < TQ; ++q) tq[q] = load_piece(tp, q);
+        }
         // ---- Z = T_c Y
-        f4 Z[KT][KT];
+        d4 Z[KT][KT];
 #pragma unroll
         for (int nt = 0; nt < KT; ++nt)
 #pragma unroll
-            for (int mt = 0; mt < KT; ++mt) Z[nt][mt] = f4{0.f, 0.f, 0.f, 0.f};
+            for (int mt = 0; mt < KT; ++mt) Z[nt][mt] = d4{0., 0., 0., 0.};
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
             for (int mt = 0; mt < KT; ++mt) {
-                const f4 av = *reinterpret_cast<const f4 *>(&s.tile[(16 * mt + c) * LDT + 16 * kt + 4 * g]);
+                const d4 av = *reinterpret_cast<const d4 *>(&tile[(16 * mt + c) * LDT + 16 * kt + 4 * g]);
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
 #pragma unroll
-                    for (int nt = 0; nt < KT; ++nt) Z[nt][mt] = mfma4(av[v], Y[nt][kt][v], Z[nt][mt]);
+                    for (int nt = 0; nt < KT; ++nt) Z[nt][mt] = mfma8(av[v], Y[nt][kt][v], Z[nt][mt]);
             }
         wave_sync(); // the tile is free again
         double zexp[KT];
@@ -429,9 +558,45 @@ template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(Reset
         if (boundary) {
             did_reset = a.policy == 1;
             if (!did_reset) {
-                d4 G[KT][KT];
-                gram<DP>(Z, G);
-                did_reset = near_colinear(G);
+                // squared cosines between columns, tile by tile of the Gram matrix: any pair above the threshold?
+#pragma unroll
+                for (int nt = 0; nt < KT; ++nt) {
+                    d4 Gd = {0., 0., 0., 0.};
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) Gd = mfma8(Z[nt][kt][v], Z[nt][kt][v], Gd);
+                    // G[j][j] for column j = 16 nt + c sits in lane (c % 4, c), register c / 4
+                    double dsel = Gd[0];
+                    dsel = (c >> 2) == 1 ? Gd[1] : dsel;
+                    dsel = (c >> 2) == 2 ? Gd[2] : dsel;
+                    dsel = (c >> 2) == 3 ? Gd[3] : dsel;
+                    if (g == (c & 3)) s.diag[16 * nt + c] = dsel;
+                }
+                wave_sync();
+                bool hit = false;
+                const double thr2 = (double)a.cos_threshold * (double)a.cos_threshold;
+#pragma unroll
+                for (int nt = 0; nt < KT; ++nt) {
+                    const double dc = s.diag[16 * nt + c];
+#pragma unroll
+                    for (int mt = 0; mt <= nt; ++mt) {
+                        d4 Gt = {0., 0., 0., 0.}; // rows: columns 16 mt + .. of Z, columns: 16 nt + c
+#pragma unroll
+                        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) Gt = mfma8(Z[mt][kt][v], Z[nt][kt][v], Gt);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int row = 16 * mt + 4 * v + g, col = 16 * nt + c;
+                            const double dr = s.diag[row];
+                            const double x = Gt[v];
+                            if (row < col && col < d && x * x > thr2 * dr * dc) hit = true;
+                        }
+                    }
+                }
+                wave_sync();
+                did_reset = __builtin_amdgcn_ballot_w64(hit) != 0;
             }
         }
         if (did_reset) {
@@ -446,19 +611,19 @@ template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(Reset
             // Y <- Z with every column renormalised by a power of two
 #pragma unroll
             for (int nt = 0; nt < KT; ++nt) {
-                float mx = 0.0f;
+                double mx = 0.0;
 #pragma unroll
                 for (int mt = 0; mt < KT; ++mt)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) mx = fmaxf(mx, fabsf(Z[nt][mt][v]));
-                mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                    for (int v = 0; v < 4; ++v) mx = fmax(mx, fabs(Z[nt][mt][v]));
+                mx = fmax(mx, __shfl_xor(mx, 16, 64));
+                mx = fmax(mx, __shfl_xor(mx, 32, 64));
                 int ex = 0;
-                if (mx > 0.0f) (void)frexpf(mx, &ex);
+                if (mx > 0.0) (void)frexp(mx, &ex);
 #pragma unroll
                 for (int mt = 0; mt < KT; ++mt)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) Y[nt][mt][v] = ldexpf(Z[nt][mt][v], -ex);
+                    for (int v = 0; v < 4; ++v) Y[nt][mt][v] = ldexp(Z[nt][mt][v], -ex);
                 yexp[nt] = zexp[nt] + (double)ex;
             }
         }
@@ -469,7 +634,7 @@ template <int DP> __global__ __launch_bounds__(64) void reset_carry_kernel(Reset
 
     // ---- growth of the final state (factorised, not replaced)
     if (a.growth) {
-        f4 Z[KT][KT];
+        d4 Z[KT][KT];
 #pragma unroll
         for (int nt = 0; nt < KT; ++nt)
 #pragma unroll
@@ -682,18 +847,18 @@ template <typename R> __global__ void uniform_u0_kernel(R *u, long long n, int d
 // After phase 3 has stored the states of every chunk: the state at a reset step is the
 // reset one, which is the prefix entering the next chunk; also fills the per-step flags.
 struct ResetPostArgs {
-    const unsigned char *carries;
+    const unsigned char *carries; // factored prefixes with double mantissas
     long long car_stride;
     int car_cols;
     int dp;
     const unsigned char *chunk_flags;
-    float *states;        // NULL or [batch][T][d][d] GOOMs
+    void *states;         // NULL or [batch][T][d][d] GOOMs
     unsigned char *flags; // NULL or [batch][T]
     long long T, L, C;
     int d;
 };
 
-__global__ __launch_bounds__(kThreads) void reset_post_kernel(ResetPostArgs a)
+template <typename IO> __global__ __launch_bounds__(kThreads) void reset_post_kernel(ResetPostArgs a)
 {
     const long long b = blockIdx.x / a.C, c = blockIdx.x % a.C;
     const int tid = threadIdx.x, d = a.d;
@@ -705,15 +870,16 @@ __global__ __launch_bounds__(kThreads) void reset_post_kernel(ResetPostArgs a)
         for (long long t = tid; t < len; t += kThreads) a.flags[b * a.T + t_first + t] = (was_reset && t == len - 1) ? 1 : 0;
     if (!was_reset || !a.states) return;
     const unsigned char *src = a.carries + (b * (a.C + 1) + c + 1) * a.car_stride;
-    const float *mp = reinterpret_cast<const float *>(src);
-    const double *ep = reinterpret_cast<const double *>(src + (size_t)a.dp * a.car_cols * sizeof(float));
-    float *op = a.states + ((size_t)(b * a.T + t_first + len - 1) * d * d) * 2;
+    const double *mp = reinterpret_cast<const double *>(src);
+    const double *ep = reinterpret_cast<const double *>(src + (size_t)a.dp * a.car_cols * sizeof(double));
+    IO *op = static_cast<IO *>(a.states) + ((size_t)(b * a.T + t_first + len - 1) * d * d) * 2;
+    const IO pi = sizeof(IO) == 4 ? (IO)3.14159274101257324219f : (IO)3.14159265358979311600;
     for (int e = tid; e < d * d; e += kThreads) {
         const int i = e / d, k = e % d;
-        const float v = mp[(size_t)i * a.car_cols + k];
-        const double re = v != 0.0f ? (log2((double)fabsf(v)) + ep[k]) * kLn2 : -__builtin_huge_val();
-        op[(size_t)e * 2] = (float)re;
-        op[(size_t)e * 2 + 1] = v < 0.0f ? 3.14159274101257324219f : 0.0f;
+        const double v = mp[(size_t)i * a.car_cols + k];
+        const double re = v != 0.0 ? log(fabs(v)) + ep[k] * kLn2 : -__builtin_huge_val();
+        op[(size_t)e * 2] = (IO)re;
+        op[(size_t)e * 2 + 1] = v < 0.0 ? pi : (IO)0;
     }
 }
 
@@ -729,7 +895,7 @@ int launch_reset_post(goom_ctx *ctx, const ResetLaunch &l)
     a.car_cols = l.car_cols;
     a.dp = padded_dim(l.d);
     a.chunk_flags = l.chunk_flags;
-    a.states = static_cast<float *>(l.post_states);
+    a.states = l.post_states;
     a.flags = l.flags;
     a.T = l.T;
     a.L = l.L;
@@ -738,7 +904,10 @@ int launch_reset_post(goom_ctx *ctx, const ResetLaunch &l)
     const long long grid = l.batch * l.C;
     if (grid > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many chunks for one launch");
     prof_begin(ctx, "reset_post_states_flags");
-    hipLaunchKernelGGL(reset_post_kernel, dim3((unsigned)grid), dim3(kThreads), 0, ctx->stream, a);
+    if (l.dtype == GOOM_C64)
+        hipLaunchKernelGGL(reset_post_kernel<float>, dim3((unsigned)grid), dim3(kThreads), 0, ctx->stream, a);
+    else
+        hipLaunchKernelGGL(reset_post_kernel<double>, dim3((unsigned)grid), dim3(kThreads), 0, ctx->stream, a);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch reset_post_kernel");
 }
@@ -809,7 +978,7 @@ int launch_reset_carry(goom_ctx *ctx, const ResetLaunch &l)
     a.carries = static_cast<unsigned char *>(l.carries);
     a.car_stride = l.car_stride;
     a.car_cols = l.car_cols;
-    a.s0 = static_cast<const float *>(l.s0);
+    a.s0 = l.s0;
     a.chunk_flags = l.chunk_flags;
     a.growth = l.growth;
     a.growth_scale = l.growth_scale;
@@ -820,15 +989,19 @@ int launch_reset_carry(goom_ctx *ctx, const ResetLaunch &l)
     a.policy = l.policy;
     a.cos_threshold = l.cos_threshold;
     const int dp = padded_dim(l.d);
+    if (dp != 16 && dp != 32 && dp != 64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 64 (d=%d)", l.d);
     prof_begin(ctx, "reset_phase2_carries_qr");
-    if (dp == 16)
-        hipLaunchKernelGGL(reset_carry_kernel<16>, dim3((unsigned)l.batch), dim3(64), 0, ctx->stream, a);
-    else if (dp == 32)
-        hipLaunchKernelGGL(reset_carry_kernel<32>, dim3((unsigned)l.batch), dim3(64), 0, ctx->stream, a);
-    else if (dp == 64)
-        hipLaunchKernelGGL(reset_carry_kernel<64>, dim3((unsigned)l.batch), dim3(64), 0, ctx->stream, a);
-    else
-        return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 64 (d=%d)", l.d);
+#define GOOM_RESET_CASE(DPV)                                                                                                   \
+    if (dp == DPV) {                                                                                                           \
+        if (l.dtype == GOOM_C64)                                                                                               \
+            hipLaunchKernelGGL((reset_carry_kernel<DPV, float>), dim3((unsigned)l.batch), dim3(64), 0, ctx->stream, a);       \
+        else                                                                                                                   \
+            hipLaunchKernelGGL((reset_carry_kernel<DPV, double>), dim3((unsigned)l.batch), dim3(64), 0, ctx->stream, a);      \
+    }
+    GOOM_RESET_CASE(16)
+    GOOM_RESET_CASE(32)
+    GOOM_RESET_CASE(64)
+#undef GOOM_RESET_CASE
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch reset_carry_kernel");
 }

@@ -268,23 +268,20 @@ def test_config4_lyapunov_full_size(G, oracle):
     states, flags, growth = G.scan_reset(Jz)
     assert np.abs(host(growth) / (T * dt) - lam).max() < 1e-9
     fl = host(flags)
-    L = 32
+    L = 128  # the library's default
     assert fl.sum() == T // L and np.all(fl[L - 1::L] == 1)
-    head = 4096
-    re, sg, oflag, _ = oracle.reset_scan(oracle.to_goom(Jr[:head]), None, check_every=L, policy=1)
-    got = host(states[:head])
-    assert np.array_equal(fl[:head], oflag)
-    top = re.max(axis=1, keepdims=True)
-    vg = np.where(got.imag != 0, -1.0, 1.0) * np.exp(got.real.astype(np.float64) - top)
-    vr = np.where(sg == 1, -1.0, 1.0) * np.exp(re - top)
-    col_err = np.linalg.norm(vg - vr, axis=1) / np.linalg.norm(vr, axis=1)
-    per_block = col_err.reshape(-1, 512, d).max(axis=(1, 2))
-    say("  column-wise relative error of the states, per 512 steps: " + " ".join(f"{v:.1e}" for v in per_block))
-    # The frame's columns belonging to nearly equal exponents relax towards their limits only at the
-    # rate of the exponents' difference, so float-level differences between the two computations
-    # persist across resets and add up like a random walk: the column-wise bound is enforced on the
-    # leading 1024 steps (32 resets); beyond them the spans still agree, which the exponents measure.
-    assert per_block[:2].max() < 5e-3 and per_block.max() < 0.1
+    # every entry of every state of the whole run against the sequentially reset oracle (both factorise in
+    # double at the same steps); the only entries left out are those below e^-10 of their column's largest (the
+    # orthonormal factor of a reset is good to about cond^2 2^-53, up to 1e-8, of a column's norm)
+    say("  sequentially reset oracle over the whole chain")
+    re, sg, oflag, _ = oracle.reset_scan(oracle.to_goom(Jr), None, check_every=L, policy=1)
+    assert np.array_equal(fl, oflag)
+    worst = 0.0
+    for t0 in range(0, T, 16384):
+        sl = slice(t0, t0 + 16384)
+        got = host(states[sl])
+        tiny = re[sl] < re[sl].max(axis=1, keepdims=True) - 10.0
+        compare(got, re[sl], sg[sl], None, name=f"config 4 states {t0}..{t0 + 16383}", max_ill_fraction=0.01, well=~tiny)
     # the last states are orthonormal right after the final reset (T is a multiple of the chunk length)
     q = host(states[T - 1])
     qv = np.where(q.imag != 0, -1.0, 1.0) * np.exp(q.real.astype(np.float64))
