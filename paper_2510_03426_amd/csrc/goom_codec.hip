@@ -4,6 +4,7 @@
 // type.  For float components that evaluation is a short series of its own (the library's
 // double routines made these kernels compute bound).
 #include "goom_internal.h"
+#include "goom_codec_tables.h"
 
 namespace {
 
@@ -97,6 +98,171 @@ __device__ inline double exp_series(double x0, double *expm1_small = nullptr, bo
     return x0 == x0 ? y : x0;                     // NaN stays
 }
 
+// ---- double-double arithmetic for the complex128 codecs --------------------------------------------------
+// The paper's codecs are the real logarithm and exponential (Section 3.1); "rounded once" for double
+// components needs more than double inside, so these two are evaluated as unevaluated sums hi + lo of two
+// doubles (about 100 significant bits), and the result is hi after the last renormalisation, i.e. the
+// double nearest the exact value except when that value lies within 2^-45 ulp or so of a rounding boundary.
+struct dd {
+    double hi, lo;
+};
+__device__ inline dd two_sum(double a, double b)
+{
+#pragma clang fp contract(off) // the error-free sums and products below need every operation rounded as written
+    const double s = a + b, bb = s - a;
+    return dd{s, (a - (s - bb)) + (b - bb)};
+}
+__device__ inline dd fast_two_sum(double a, double b) // |a| >= |b|
+{
+#pragma clang fp contract(off) // the error-free sums and products below need every operation rounded as written
+    const double s = a + b;
+    return dd{s, b - (s - a)};
+}
+__device__ inline dd two_prod(double a, double b)
+{
+#pragma clang fp contract(off) // the error-free sums and products below need every operation rounded as written
+    const double p = a * b;
+    return dd{p, __builtin_fma(a, b, -p)};
+}
+__device__ inline dd dd_add(dd x, dd y)
+{
+#pragma clang fp contract(off) // the error-free sums and products below need every operation rounded as written
+    dd s = two_sum(x.hi, y.hi);
+    const dd t = two_sum(x.lo, y.lo);
+    s.lo += t.hi;
+    s = fast_two_sum(s.hi, s.lo);
+    s.lo += t.lo;
+    return fast_two_sum(s.hi, s.lo);
+}
+__device__ inline dd dd_add_d(dd x, double y)
+{
+#pragma clang fp contract(off) // the error-free sums and products below need every operation rounded as written
+    dd s = two_sum(x.hi, y);
+    s.lo += x.lo;
+    return fast_two_sum(s.hi, s.lo);
+}
+__device__ inline dd dd_mul(dd x, dd y)
+{
+#pragma clang fp contract(off) // the error-free sums and products below need every operation rounded as written
+    dd p = two_prod(x.hi, y.hi);
+    p.lo = __builtin_fma(x.hi, y.lo, __builtin_fma(x.lo, y.hi, p.lo));
+    return fast_two_sum(p.hi, p.lo);
+}
+__device__ inline dd dd_mul_d(dd x, double y)
+{
+#pragma clang fp contract(off) // the error-free sums and products below need every operation rounded as written
+    dd p = two_prod(x.hi, y);
+    p.lo = __builtin_fma(x.lo, y, p.lo);
+    return fast_two_sum(p.hi, p.lo);
+}
+
+// ln|x| for a finite non-zero double x, as a double-double.  x = m 2^k with m in [sqrt(1/2), sqrt(2));
+// m = c (1 + r) with 1 / c a 24-bit table value near 1 / m (so m / c - 1 is formed exactly, |r| < 0.0056, and
+// c = 1 for m next to 1, where the result keeps its relative accuracy); ln(1 + r) = 2 atanh(s), s = r / (2 + r),
+// |s| < 2^-8.4: s + s^3 / 3 + ... to s^15 (remainder 2^-140 relative), the leading terms in double-double.
+__device__ inline dd ln_abs_dd(double x)
+{
+#pragma clang fp contract(off) // the error-free sums and products below need every operation rounded as written
+    using namespace goom_codec_tables;
+    int k;
+    double m = __builtin_frexp(__builtin_fabs(x), &k); // [1/2, 1)
+    const bool low = m < 0.70710678118654752440;
+    m = low ? m + m : m;
+    k = low ? k - 1 : k;
+    const int i = (int)__builtin_rint((m - 1.0) * 128.0);
+    const double *tab = kLogTab[i - kLogIndexMin];
+    const dd p = two_prod(m, tab[0]);
+    dd r = fast_two_sum(p.hi - 1.0, p.lo); // exact: p.hi is within 2^-7 of 1
+    // s = r / (2 + r)
+    dd den = two_sum(2.0, r.hi);
+    den.lo += r.lo;
+    double inv = (double)__builtin_amdgcn_rcpf((float)den.hi);
+    inv = inv * (2.0 - den.hi * inv);
+    inv = inv * (2.0 - den.hi * inv);
+    const double q1 = r.hi * inv;
+    // remainder r - q1 den, exactly enough: q1 den.hi as a product pair
+    const dd qd = two_prod(q1, den.hi);
+    const double rem = ((r.hi - qd.hi) - qd.lo) + (r.lo - q1 * den.lo);
+    const dd s = fast_two_sum(q1, rem * inv);
+    const dd z = dd_mul(s, s);
+    // s^2 (1/3 + z/5 + z^2/7 + z^3/9 + ...): the tail from z^3/9 on in double
+    double tail = 1.0 / 15.0;
+    tail = __builtin_fma(tail, z.hi, 1.0 / 13.0);
+    tail = __builtin_fma(tail, z.hi, 1.0 / 11.0);
+    tail = __builtin_fma(tail, z.hi, 1.0 / 9.0);
+    dd poly = dd_add(dd_mul_d(z, tail), dd{kInv7Hi, kInv7Lo});
+    poly = dd_add(dd_mul(poly, z), dd{kInv5Hi, kInv5Lo});
+    poly = dd_add(dd_mul(poly, z), dd{kInv3Hi, kInv3Lo});
+    dd lg = dd_mul(dd_mul(poly, z), s); // s^3 (1/3 + ...)
+    lg = dd_add(s, lg);
+    lg.hi *= 2.0;
+    lg.lo *= 2.0;
+    // + ln c + k ln 2, largest parts first (k ln 2 in three parts, the first exact)
+    const double kd = (double)k;
+    dd acc = two_prod(kd, kLn2B);
+    acc = dd_add_d(acc, kd * kLn2C);
+    acc = dd_add(dd{kd * kLn2A, 0.0}, acc);
+    acc = dd_add(acc, dd{tab[1], tab[2]});
+    return dd_add(acc, lg);
+}
+
+// e^x for |x| < 746 as a double-double times 2^k: x = (64 k + j) ln2 / 64 + r, |r| < 0.0055 (the step in three
+// parts, the first with 32 significant bits so that its multiple is exact); e^r = 1 + r + r^2 (1/2 + r/6 + ...) to
+// r^12, the leading terms in double-double; times the table value 2^(j / 64).
+__device__ inline dd exp_dd(double x, int &k)
+{
+#pragma clang fp contract(off) // the error-free sums and products below need every operation rounded as written
+    using namespace goom_codec_tables;
+    const double nd = __builtin_rint(x * kExpInvStep);
+    const int n = (int)nd;
+    k = n >> 6;
+    const int j = n & 63;
+    const double r1 = __builtin_fma(-nd, kExpStepA, x); // exact
+    const dd pb = two_prod(nd, kExpStepB);
+    dd r = two_sum(r1, -pb.hi);
+    r.lo -= pb.lo + nd * kExpStepC;
+    r = fast_two_sum(r.hi, r.lo);
+    double tail = 1.0 / 479001600.0;
+    tail = __builtin_fma(tail, r.hi, 1.0 / 39916800.0);
+    tail = __builtin_fma(tail, r.hi, 1.0 / 3628800.0);
+    tail = __builtin_fma(tail, r.hi, 1.0 / 362880.0);
+    tail = __builtin_fma(tail, r.hi, 1.0 / 40320.0);
+    tail = __builtin_fma(tail, r.hi, 1.0 / 5040.0);
+    tail = __builtin_fma(tail, r.hi, 1.0 / 720.0);
+    dd poly = dd_add(dd_mul_d(r, tail), dd{kInvF120Hi, kInvF120Lo});
+    poly = dd_add(dd_mul(poly, r), dd{kInvF24Hi, kInvF24Lo});
+    poly = dd_add(dd_mul(poly, r), dd{kInvF6Hi, kInvF6Lo});
+    poly = dd_add_d(dd_mul(poly, r), 0.5);
+    dd q = dd_mul(dd_mul(poly, r), r); // r^2 (1/2 + ...)
+    q = dd_add(r, q);                  // e^r - 1
+    const dd t = dd{kExpTab[j][0], kExpTab[j][1]};
+    return dd_add(t, dd_mul(t, q));
+}
+
+// exp of a double log-magnitude, rounded once (also into the subnormal range)
+__device__ inline double exp_rounded_once(double x)
+{
+#pragma clang fp contract(off) // the error-free sums and products below need every operation rounded as written
+    if (!(x == x)) return x;
+    if (x > 709.79) return __builtin_huge_val();
+    if (x < -745.14) return 0.0;
+    int k;
+    const dd y = exp_dd(x, k); // value (y.hi + y.lo) 2^k, y.hi in [1, 2)
+    if (k > -1022) { // normal result: a power-of-two scaling of an already rounded hi (1024 cannot happen below 709.79)
+        return __builtin_ldexp(y.hi, k);
+    }
+    // subnormal result: the value in units of 2^-1074 is w = (y.hi + y.lo) 2^(k + 1074) < 2^52; adding 2^52 rounds
+    // w's high part to a whole number, and what that addition and y.lo leave decides the last unit
+    const double whi = __builtin_ldexp(y.hi, k + 1074), wlo = __builtin_ldexp(y.lo, k + 1074);
+    const double big = 4503599627370496.0; // 2^52
+    const double sh = big + whi;
+    double nint = sh - big;
+    const double left = (whi - nint) + wlo; // exact difference plus the low part
+    if (left > 0.5 || (left == 0.5 && __builtin_fmod(nint, 2.0) != 0.0)) nint += 1.0;
+    if (left < -0.5 || (left == -0.5 && __builtin_fmod(nint, 2.0) != 0.0)) nint -= 1.0;
+    return __builtin_ldexp(nint, -1074);
+}
+
 __device__ inline double exp_of_f32(float xf) { return exp_series((double)xf); }
 
 // (straight-line: the series runs on every input, zeros, infinities and NaN included, and the special results
@@ -140,7 +306,10 @@ __global__ __launch_bounds__(256) void to_goom_f64_kernel(const double *__restri
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         double v = x[i];
-        double re = (v == 0.0) ? (zero_floor ? kFloorF64 : -__builtin_huge_val()) : log(__builtin_fabs(v));
+        const double av = __builtin_fabs(v);
+        double re = ln_abs_dd(av < __builtin_huge_val() ? (av > 0.0 ? av : 1.0) : 1.0).hi;
+        re = av < __builtin_huge_val() ? re : av; // infinities and NaN pass through
+        re = (v == 0.0) ? (zero_floor ? kFloorF64 : -__builtin_huge_val()) : re;
         double2 o;
         o.x = re;
         o.y = v < 0.0 ? kPiD : 0.0;
@@ -171,7 +340,7 @@ __global__ __launch_bounds__(256) void from_goom_f64_kernel(const double *__rest
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         double2 z = reinterpret_cast<const double2 *>(y)[i];
-        double mag = exp(z.x);
+        double mag = exp_rounded_once(z.x);
         x[i] = odd_multiple_of_pi(z.y) ? -mag : mag;
     }
 }

@@ -234,6 +234,31 @@ def test_config3_batched_lmme_full_size(G, oracle, ctype):
     del a, b, c
 
 
+def test_codecs_float_sweep_of_bit_patterns(G, oracle):
+    """Float codecs over 2^28 of the 2^32 bit patterns, one from every run of sixteen consecutive patterns (so
+    every exponent, the subnormals, both signs, infinities and NaNs): as inputs of to_goom, and as log-magnitudes
+    of from_goom.  Equal bits throughout; stops at the first block with a mismatch."""
+    block = 1 << 24
+    for blk in range(16):
+        i = np.arange(blk * block, (blk + 1) * block, dtype=np.uint64)
+        bits = (i * 16 + (i * 7 + blk) % 16).astype(np.uint32)
+        x = bits.view(np.float32)
+        want = oracle.to_goom(x)
+        got = host(G.to_goom(dev(x)))
+        a, b = got.view(np.uint32).reshape(-1, 2), want.view(np.uint32).reshape(-1, 2)
+        nan = np.isnan(x)
+        neq = (a != b).any(axis=1) & ~nan
+        assert not neq.any(), f"block {blk}: {neq.sum()} encodings differ, first at bits {bits[np.argwhere(neq)[0, 0]]:#x}"
+        assert np.all(np.isnan(got.real[nan]))
+        z = (x.astype(np.complex64) + np.complex64(1j * np.pi) * (bits & 1).astype(np.float32)).astype(np.complex64)
+        z.imag[...] = np.where((bits & 1) != 0, np.float32(np.pi), np.float32(0))
+        want = oracle.from_goom(z)
+        got = host(G.from_goom(dev(z)))
+        neq = (got.view(np.uint32) != want.view(np.uint32)) & ~nan
+        assert not neq.any(), f"block {blk}: {neq.sum()} decodings differ, first at bits {bits[np.argwhere(neq)[0, 0]]:#x}"
+        say(f"  codec sweep block {blk + 1}/16: {block} patterns equal in both directions")
+
+
 def test_config4_lyapunov_full_size(G, oracle):
     T, d, dt = 131072, 32, 0.01
     say(f"config 4 at full size: Lorenz-96 d={d}, T={T}")

@@ -122,36 +122,32 @@ def compare(got, ref_re, ref_sg, kappa=None, name="", max_ill_fraction=0.005, we
 def test_codecs_bit_exact(G, oracle, comp):
     rng = np.random.default_rng(101)
     n = (1 << 20) + 3  # ragged tail
-    x = np.concatenate([
-        si.normal_f32(si.BASE_SEED, 50, n // 2).astype(comp),
-        (np.exp(rng.uniform(-85, 85, n - n // 2 - 8)) * rng.choice([-1.0, 1.0], n - n // 2 - 8)).astype(comp),
-        np.array([0.0, -0.0, 1.0, -1.0, np.inf, -np.inf, np.finfo(comp).tiny, -np.finfo(comp).max], dtype=comp),
-    ])
+    span = 85.0 if comp == np.float32 else 705.0
+    tiny = np.finfo(comp).tiny
+    special = np.array([0.0, -0.0, 1.0, -1.0, np.inf, -np.inf, tiny, -np.finfo(comp).max, tiny / 8, -tiny / 1024,
+                        np.nextafter(comp(1), comp(2)), np.nextafter(comp(1), comp(0)), 2.0, 0.5, np.sqrt(comp(2)), np.sqrt(comp(0.5))], dtype=comp)
+    near_one = (1.0 + rng.uniform(-1e-3, 1e-3, 4096)).astype(comp)
+    wide = (np.exp(rng.uniform(-span, span, n - n // 2 - special.size - near_one.size)) * rng.choice([-1.0, 1.0], n - n // 2 - special.size - near_one.size)).astype(comp)
+    x = np.concatenate([si.normal_f32(si.BASE_SEED, 50, n // 2).astype(comp), wide, near_one, special])
     say(f"codec {comp.__name__}: n={x.size}")
+    word = np.uint32 if comp == np.float32 else np.uint64
     for flags in (0, 1):
         want = oracle.to_goom(x, zero_floor=bool(flags))
         got = host(G.to_goom(dev(x), flags=flags))
-        if comp == np.float32:
-            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), \
-                f"{np.sum(got.view(np.uint32) != want.view(np.uint32))} words differ"
-        else:
-            # double components: both sides round a correctly rounded double log once; equal bits expected
-            # except where two different double-precision logs disagree in the last place
-            neq = got.view(np.uint64) != want.view(np.uint64)
-            ulp = np.abs(got.real - want.real) / np.maximum(np.spacing(np.abs(want.real)), 5e-324)
-            say(f"  double codec: {neq.sum()} of {neq.size} words differ, max {np.nanmax(np.where(np.isfinite(ulp), ulp, 0)):.1f} ulp")
-            assert np.array_equal(got.imag, want.imag)
-            assert np.all((ulp <= 1.0) | ~np.isfinite(want.real))
+        neq = got.view(word) != want.view(word)
+        assert not neq.any(), f"{neq.sum()} encoded words differ, first at x = {x[np.argwhere(neq.reshape(-1, 2).any(axis=1))[0, 0]]!r}"
     z = oracle.to_goom(x)
     z = z[np.isfinite(z.real) | np.isneginf(z.real)]
+    # log-magnitudes of their own too: the whole range of results, subnormal ones and both ends included
+    lo, hi = (-104.0, 89.0) if comp == np.float32 else (-746.0, 710.0)
+    extra = rng.uniform(lo, hi, 1 << 18).astype(comp) + (1j * np.pi * rng.integers(0, 2, 1 << 18)).astype(z.dtype)
+    extra.imag[...] = np.where(extra.imag != 0, comp(np.pi), comp(0))
+    edge = rng.uniform(lo, lo + 42.0, 1 << 16).astype(comp).astype(z.dtype)  # results below the smallest normal
+    z = np.concatenate([z, extra.astype(z.dtype), edge])
     want = oracle.from_goom(z)
     got = host(G.from_goom(dev(z)))
-    if comp == np.float32:
-        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), \
-            f"{np.sum(got.view(np.uint32) != want.view(np.uint32))} decoded words differ"
-    else:
-        ulp = np.abs(got - want) / np.spacing(np.abs(want))
-        assert np.all(ulp <= 1.0)
+    neq = got.view(word) != want.view(word)
+    assert not neq.any(), f"{neq.sum()} decoded words differ, first at z = {z[np.argwhere(neq)[0, 0]]!r}: {got[np.argwhere(neq)[0, 0]]!r} vs {want[np.argwhere(neq)[0, 0]]!r}"
     # empty input
     import torch
     assert G.to_goom(torch.empty(0, dtype=torch.float32, device="cuda")).numel() == 0
