@@ -31,7 +31,8 @@ def main():
     ap.add_argument("--cpu-sample-steps", type=int, default=16384,
                     help="leading steps of the chain the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
-                    help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs")
+                    help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (default: looked up in "
+                         "the counter summaries under profiles/ for this kernel and workload, null when there is none)")
     ap.add_argument("--no-extras", action="store_true", help="time the headline scan only")
     ap.add_argument("--only", choices=["tiny", "between", "scan128", "complex128", "lmme", "lyapunov", "recurrence", "large"], default=None,
                     help="time just one of the other workloads (for profiler runs) and print its figures")
@@ -81,12 +82,19 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # every step bracketed by events on the stream the library launches on (the context's stream is torch's current one)
+    stream = torch.cuda.current_stream(dev)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for a, b in ev:
+        a.record(stream)
         step()
+        b.record(stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
+    step_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    ms_median = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else 0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
     products_per_s = T / (ms_per_step * 1e-3)
 
     # ---- per-kernel durations from HIP events on the library's stream
@@ -110,16 +118,16 @@ def main():
     else:
         alg_bytes = T * 8 * d * d
     achieved_gbs = alg_bytes / (kern_avg[dominant] * 1e-3) / 1e9
-    # HBM bytes per launch of that kernel from the FETCH_SIZE / WRITE_SIZE counter runs on this
-    # workload (64.02 KiB per product for the fix-up kernel at d = 64, default chunking: FETCH_SIZE
-    # scaled by 2 and WRITE_SIZE by 1, the factors a plain copy of known size gives)
-    traffic = args.traffic_bytes
-    if traffic is None and d == 64 and args.chunk_len == 0 and dominant.endswith("fixup_outputs"):
-        traffic = round(T * 64.02 * 1024)
+    # HBM bytes per launch of that kernel as the FETCH_SIZE / WRITE_SIZE counters measured them in separate
+    # rocprofv3 --pmc runs of this command: looked up in the tracked counter summaries (profiles/), by kernel and
+    # workload; null when no summary covers this run
+    traffic, traffic_source = args.traffic_bytes, "--traffic-bytes" if args.traffic_bytes is not None else None
+    if traffic is None:
+        traffic, traffic_source = traffic_from_profiles(dominant, T, d, args.chunk_len)
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-        "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
+        "traffic": traffic, "traffic_source": traffic_source, "algorithmic_bytes_per_launch": alg_bytes,
         "avg_launch_ms": round(kern_avg[dominant], 4),
     }
     # matrix-core work actually executed: one d^3 product per matrix in phase 1, one per chunk in
@@ -130,9 +138,12 @@ def main():
                     if "phase1" in k or "phase3" in k}
 
     result = {
-        "metric": "GOOM matrix products scanned per second (inclusive prefix scan, all prefixes stored)",
+        "metric": "d\u00d7d GOOM matrix products scanned/sec; LMME TFLOP/s as % of MFMA peak",
         "value": round(products_per_s, 1), "unit": "products/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_events": {"median": round(ms_median, 4), "mean": round(sum(step_ms) / len(step_ms), 4),
+                               "min": round(step_ms[0], 4), "max": round(step_ms[-1], 4)},
+        "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"prefix scan of T={T} real {d}x{d} N(0,1) matrices as complex64 GOOMs, "
                                f"in HBM, {T * d * d * 8 / 1e9:.1f} GB in and out",
@@ -232,6 +243,25 @@ def main():
         result["cpu_baseline"]["gpu_entries_within_tolerance"] = round(float(np.mean(err <= tol)), 6)
 
     print(json.dumps(result), flush=True)
+
+
+def traffic_from_profiles(kernel_label, T, d, chunk_len):
+    """HBM bytes per launch of a kernel from the counter summaries under profiles/: lines of the form
+    'traffic_bytes_per_launch kernel=<label> T=<T> d=<d> chunk_len=<L> bytes=<N>'.  Returns (bytes, source) or (None, None)."""
+    import glob
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    for path in sorted(glob.glob(os.path.join(here, "profiles", "*.txt"))):
+        with open(path) as f:
+            for line in f:
+                if not line.startswith("traffic_bytes_per_launch "):
+                    continue
+                kv = dict(item.split("=", 1) for item in line.split()[1:])
+                if (kv.get("kernel") == kernel_label and int(kv.get("T", -1)) == T and int(kv.get("d", -1)) == d
+                        and int(kv.get("chunk_len", -1)) == chunk_len):
+                    return int(kv["bytes"]), ("profiles/" + os.path.basename(path) + ": rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, "
+                                              "each scaled by what the same counter reads for a plain copy of known size")
+    return None, None
 
 
 def timed(torch, fn, reps=3):
@@ -483,7 +513,7 @@ def recurrence(g, torch, dev, si):
     bz = g.to_goom(torch.randn((nseq, T, d), device=dev, generator=si.device_generator(251003426 * 10 + 52, dev)))
     h = torch.empty((nseq, T, d), dtype=torch.complex64, device=dev)
     sec = timed(torch, lambda: g.affine_scan(az, bz, out=h))
-    byts = (az.numel() + bz.numel() + h.numel()) * 8
+    byts = (2 * az.numel() + 2 * bz.numel() + h.numel()) * 8  # the matrices and the inputs are read by two phases
     res["recurrence_128seq_T65536_d32"] = {
         "ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1),
         "hbm_gbs_algorithmic": round(byts / sec / 1e9, 1), "pct_of_hbm_peak": round(100 * byts / sec / 1e9 / HBM_PEAK_GBS, 2),

@@ -31,7 +31,7 @@
  *
  * Range of the product calls.  Inside a product the factors are exponentiated after a
  * per-row shift of the left factor and a per-column shift of the right factor (paper
- * Section 3.2, eq. 7), so within one row-by-column sum terms smaller than the largest
+ * Section 3.2, eq. 10), so within one row-by-column sum terms smaller than the largest
  * possible term by more than the component format's range (about e^-87 for GOOM_C64,
  * e^-708 for GOOM_C128) are dropped, as in the paper's own implementation.
  * goom_lmme can be asked to repair such sums exactly (GOOM_LMME_EXACT).
@@ -77,9 +77,9 @@ typedef enum goom_dtype {
 #define GOOM_ZERO_FLOOR 1u   /* log 0 = 2 log(smallest normal): finite, exponentiates to 0 */
 
 /* flags of goom_lmme */
-#define GOOM_LMME_FAST 0u  /* scaled real product only (paper Section 3.2, eq. 7) */
+#define GOOM_LMME_FAST 0u  /* scaled real product only (paper Section 3.2, eq. 10) */
 #define GOOM_LMME_EXACT 1u /* additionally recompute, by a signed log-sum-exp over the
-                              terms (eq. 6), every output whose scaled product lost
+                              terms (eq. 9, the definition), every output whose scaled product lost
                               terms to underflow */
 
 /* ---- context ------------------------------------------------------------------- */
@@ -132,7 +132,7 @@ int goom_probe_matrix_unit(goom_ctx *ctx, void *sink, int64_t iters, int dtype);
 int goom_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, uint32_t flags);
 
 /* GOOMs -> real floats: x[i] = +-exp(Re y[i]), the real part of the complex exponential
- * (paper Section 3.1, eq. 4); overflow gives +-inf, underflow +-0. */
+ * (paper Section 3.1, eq. 7); overflow gives +-inf, underflow +-0. */
 int goom_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype);
 
 /* ---- LMME (paper Section 3.2) ---------------------------------------------------- */
@@ -140,7 +140,7 @@ int goom_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype);
 /* C[b] = LMME(A[b], B[b]) = log(exp(A[b]) exp(B[b])) for b < batch.
  * A: [batch, n, d], B: [batch, d, m], C: [batch, n, m] GOOMs; 1 <= n, d, m <= GOOM_MAX_DIM_LMME
  * (above GOOM_MAX_DIM the workspace is required, and batch <= 65535).
- * Computed as the paper's scaled real product on the matrix cores (eq. 7) with row
+ * Computed as the paper's scaled real product on the matrix cores (eq. 10) with row
  * shifts max_j Re A_ij and column shifts max_j Re B_jk (0 for an all-zero row/column).
  * A sum that is exactly zero gives (-inf, 0).  flags: GOOM_LMME_FAST or GOOM_LMME_EXACT.
  * workspace: goom_lmme_workspace_bytes(...) bytes (may be 0 -> NULL allowed).  For n = d = m = 128 with
@@ -158,7 +158,7 @@ typedef struct goom_scan_opts {
     uint32_t flags;    /* 0, or GOOM_AFFINE_TIME_INVARIANT for goom_affine_scan */
 } goom_scan_opts;
 
-/* Inclusive prefix products, newer factor on the left (paper eq. 9):
+/* Inclusive prefix products, newer factor on the left (paper Section 4.1, eq. 14):
  *     P[b, 0] = LMME(M[b, 0], init[b])      (or M[b, 0] itself when init is NULL)
  *     P[b, t] = LMME(M[b, t], P[b, t-1])
  * M: [batch, T, d, d]; init: NULL or [batch, d, m] (m != d allowed, e.g. a vector u_0,
@@ -191,7 +191,7 @@ int goom_scan_static(goom_ctx *ctx, const void *M, const void *init, void *P, in
 
 /* Only the last prefix: P_final[b] = P[b, T-1] of goom_scan ([batch, d, m]); phases 1 and
  * 2 only, so the input is read once (the product inside the paper's largest-exponent
- * formula, Section 4.2.2, eq. 17). */
+ * formula, Section 4.2.2, eq. 24). */
 int goom_reduce(goom_ctx *ctx, const void *M, const void *init, void *P_final, int64_t T, int d,
                 int m, int64_t batch, int dtype, const goom_scan_opts *opts, void *workspace,
                 size_t workspace_bytes);
@@ -256,7 +256,7 @@ size_t goom_scan_reset_workspace_bytes(int64_t T, int d, int64_t batch, int dtyp
                                        const goom_reset_opts *opts);
 
 /* Lyapunov spectrum from the reset scan: lambda[b, k] = growth[b, k] / (dt T)
- * (paper eq. 12 with the triangular factors accumulated at the resets).  states is
+ * (paper Section 4.2.1, eq. 20, with the triangular factors accumulated at the resets).  states is
  * optional here (NULL = do not store them).  lambda: [batch, d] doubles. */
 int goom_lyapunov_spectrum(goom_ctx *ctx, const void *J, const void *S0, void *states,
                            double *lambda, int64_t T, int d, double dt, int64_t batch, int dtype,
@@ -288,14 +288,14 @@ int goom_largest_lyapunov(goom_ctx *ctx, const void *J, const void *u0, double *
 size_t goom_largest_lyapunov_workspace_bytes(int64_t T, int d, int64_t batch, int dtype,
                                              const goom_scan_opts *opts);
 
-/* ---- linear recurrence with bias (paper Section 4.3, eqs. 18 and 20) ---------------- */
+/* ---- linear recurrence with bias (paper Section 4.3, eqs. 25 and 26) ---------------- */
 
 /* Signed log-add, elementwise: out[i] is the GOOM of exp(x[i]) + exp(y[i]) (paper Section 2,
- * Example 2; the step that adds the input term in eq. 20).  x, y, out: n GOOMs each; out may
+ * Example 2; the step that adds the input term in eq. 26).  x, y, out: n GOOMs each; out may
  * alias x or y.  Equal magnitudes of opposite sign give zero, (-inf, 0). */
 int goom_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, size_t n, int dtype);
 
-/* Scaled exponentiation of GOOM vectors (paper Section 4.3, eq. 21), the way recurrence states
+/* Scaled exponentiation of GOOM vectors (paper Section 4.3, eq. 27), the way recurrence states
  * return to a floating-point format: for each of n_vectors vectors z[v, 0..d-1],
  * c = max_i Re z[v, i] and scaled[v, i] = (+-) exp(Re z[v, i] - c + 2), so all results lie in
  * [-e^2, e^2] whatever the magnitude of the state.  z: [n_vectors, d] GOOMs; scaled:
@@ -320,7 +320,7 @@ size_t goom_affine_scan_workspace_bytes(int64_t T, int d, int64_t batch, int dty
                                         const goom_scan_opts *opts);
 
 /* The same recurrence with its states returned in scaled floating-point form (paper Section 4.3,
- * eq. 21), the format the layers after the recurrence consume: scaled[b, t, i] =
+ * eq. 27), the format the layers after the recurrence consume: scaled[b, t, i] =
  * (+-) exp(Re h[b, t, i] - c[b, t] + 2) with c[b, t] = max_i Re h[b, t, i], all within
  * [-e^2, e^2].  scaled: [batch, T, d] reals of the component type; logscale: NULL or [batch, T]
  * reals receiving c (-inf for a zero state, whose scaled entries are 0).  Arguments otherwise as

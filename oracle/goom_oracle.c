@@ -11,13 +11,13 @@
  *     multiple of pi for x >= 0 and an odd multiple for x < 0; zero is non-negative
  *     (Section 2, eq. 1 and the paragraph after it);
  *   - float -> GOOM and GOOM -> float maps (Section 3.1);
- *   - LMME(A', B') = log(exp(A') exp(B')) = LSE_j(A'_ij + B'_jk) (Section 3.2, eq. 6),
+ *   - LMME(A', B') = log(exp(A') exp(B')) = LSE_j(A'_ij + B'_jk) (Section 3.2, eq. 9),
  *     written here in its definitional signed log-sum-exp form (Example 2), never the
- *     scaled-matmul shortcut of eq. 7;
+ *     scaled-matmul shortcut of eq. 10;
  *   - matrix-product chains S'_t = LMME(A'_t, S'_{t-1}) (Section 4.1);
  *   - the linear recurrence with bias used for non-diagonal state-space models
- *     (Section 4.3, eqs. 18 and 20);
- *   - sequential QR estimation of Lyapunov spectra (Section 4.2.1, eqs. 12-13) and
+ *     (Section 4.3, eqs. 25 and 26);
+ *   - sequential QR estimation of Lyapunov spectra (Section 4.2.1, eqs. 19-20) and
  *     the selectively reset recurrence (Section 5; Appendix C).
  *
  * Arithmetic: log-magnitudes are held in IEEE double, signs as one byte (0 = +, 1 = -).
@@ -126,7 +126,7 @@ ORACLE_API void oracle_to_goom_f64(const double *x, double *y, size_t n, int zer
 }
 
 /* (re, im) -> Re(exp(re + i im)) = +-exp(re); the imaginary part of the complex
- * exponential is dropped (Section 3.1, eq. 4). */
+ * exponential is dropped (Section 3.1, eq. 7). */
 ORACLE_API void oracle_from_goom_f32(const float *y, float *x, size_t n)
 {
 #pragma omp parallel for schedule(static)
@@ -168,7 +168,7 @@ ORACLE_API void oracle_split_c128(const double *z, double *re, uint8_t *sg, size
 }
 
 /* ------------------------------------------------------------------------- */
-/* signed log-sum-exp (Example 2) and LMME (Section 3.2, eq. 6)               */
+/* signed log-sum-exp (Example 2) and LMME (Section 3.2, eq. 9)               */
 /* ------------------------------------------------------------------------- */
 
 /* log of sum_j (+-)exp(z_j).  Returns the log-magnitude, the sign, and
@@ -246,7 +246,7 @@ ORACLE_API void oracle_lmme_batched(const double *are, const uint8_t *asg, const
 }
 
 /* ------------------------------------------------------------------------- */
-/* chain of matrix products (Section 4.1, eqs. 8-9)                           */
+/* chain of matrix products (Section 4.1, eqs. 14-15)                         */
 /* ------------------------------------------------------------------------- */
 
 /* Inclusive prefix products, newer factor on the left:
@@ -402,12 +402,12 @@ ORACLE_API void oracle_scan_scaled_stream(const double *mre, const uint8_t *msg,
 }
 
 /* ------------------------------------------------------------------------- */
-/* linear recurrence with bias over GOOMs (Section 4.3, eqs. 18 and 20)       */
+/* linear recurrence with bias over GOOMs (Section 4.3, eqs. 25 and 26)       */
 /* ------------------------------------------------------------------------- */
 
 /* h_t = A_t h_{t-1} + b_t, t = 1..T, h_0 given (NULL = zero vector).
  * In GOOM form each entry of h_t is the signed log-sum-exp of the d products
- * A'_t[i, j] + h'_{t-1}[j] together with b'_t[i]; that is eq. 20 with the inner LMMEs
+ * A'_t[i, j] + h'_{t-1}[j] together with b'_t[i]; that is eq. 26 with the inner LMMEs
  * written out.  A is [T, d, d], b is [T, d], h is [T, d]. */
 ORACLE_API void oracle_affine_scan(const double *are, const uint8_t *asg, const double *bre,
                                    const uint8_t *bsg, const double *h0re, const uint8_t *h0sg,
@@ -519,7 +519,7 @@ ORACLE_API void oracle_qr(const double *a, double *q, double *r, int d)
 }
 
 /* ------------------------------------------------------------------------- */
-/* Lyapunov spectrum, sequential QR (Section 4.2.1, eqs. 12-13)               */
+/* Lyapunov spectrum, sequential QR (Section 4.2.1, eqs. 19-20)               */
 /* ------------------------------------------------------------------------- */
 
 /* J: [T, d, d] real Jacobians (double).  Q_0 = I.  S_t = J_t Q_{t-1};
@@ -661,7 +661,7 @@ ORACLE_API void oracle_reset_scan(const double *jre, const uint8_t *jsg, const d
 }
 
 /* ------------------------------------------------------------------------- */
-/* the literal tuple combine of Section 5, eq. 21, over plain reals           */
+/* the literal tuple combine of Section 5, eq. 28, over plain reals           */
 /* ------------------------------------------------------------------------- */
 
 /* One application of the selective-resetting transformation to a pair of tuples
@@ -756,7 +756,7 @@ ORACLE_API void oracle_lyapunov_from_states(const double *prev_re, const uint8_t
 /* largest Lyapunov exponent (Section 4.2.2)                                  */
 /* ------------------------------------------------------------------------- */
 
-/* The standard method (eqs. 14-15): s_t = J_t u_{t-1}, u_t = s_t / |s_t|,
+/* The standard method (eqs. 21-22): s_t = J_t u_{t-1}, u_t = s_t / |s_t|,
  * LLE = sum_t log(|s_t| / |u_{t-1}|) / (dt T).  Real Jacobians, double. */
 ORACLE_API double oracle_lle_standard(const double *J, const double *u0, long T, int d, double dt)
 {
@@ -783,7 +783,7 @@ ORACLE_API double oracle_lle_standard(const double *J, const double *u0, long T,
     return (double)(acc / ((long double)dt * (long double)T));
 }
 
-/* The un-normalised form over GOOMs (eq. 17): LSE(2 * log-magnitudes of J_T ... J_1 u_0) / (2 dt T),
+/* The un-normalised form over GOOMs (eq. 24): LSE(2 * log-magnitudes of J_T ... J_1 u_0) / (2 dt T),
  * given the final vector of that product in working form (from the scan oracle). */
 ORACLE_API double oracle_lle_from_final(const double *fre, long T, int d, double dt)
 {
@@ -797,7 +797,7 @@ ORACLE_API double oracle_lle_from_final(const double *fre, long T, int d, double
 }
 
 /* ------------------------------------------------------------------------- */
-/* scaled exponentiation of recurrence states (Section 4.3, eq. 21)           */
+/* scaled exponentiation of recurrence states (Section 4.3, eq. 27)           */
 /* ------------------------------------------------------------------------- */
 
 /* For each of n vectors of length d in working form: c = max of the log-magnitudes,
@@ -820,7 +820,7 @@ ORACLE_API void oracle_scaled_exp(const double *re, const uint8_t *sg, double *s
 
 /* ------------------------------------------------------------------------- */
 /* signed log-add of two GOOM arrays: log(exp(x') + exp(y')) (Section 2, Example 2; */
-/* the bias step of Section 4.3, eq. 20)                                      */
+/* the bias step of Section 4.3, eq. 26)                                      */
 /* ------------------------------------------------------------------------- */
 
 /* Elementwise.  With m the larger and l the smaller log-magnitude, delta = m - l >= 0:

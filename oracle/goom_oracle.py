@@ -118,7 +118,7 @@ def _as_working(z):
 # ------------------------------------------------------------------------------- LMME
 
 def lmme(a, b, return_kappa: bool = False):
-    """LMME over the last two axes; leading axes are a batch (Section 3.2, eq. 6)."""
+    """LMME over the last two axes; leading axes are a batch (Section 3.2, eq. 9)."""
     are, asg = _as_working(a)
     bre, bsg = _as_working(b)
     n, d = are.shape[-2:]
@@ -275,7 +275,7 @@ def reset_scan(jac, x0=None, check_every: int = 0, policy: int = 1, cos_threshol
 
 
 def reset_combine_real(a_prev, b_prev, a_curr, b_curr, select_prev: bool, reset_value):
-    """One application of the tuple transformation of Section 5 (eq. 21) on real matrices.
+    """One application of the tuple transformation of Section 5 (eq. 28) on real matrices.
     Returns the updated (a_prev, b_prev, a_curr, b_curr)."""
     ap, bp, ac, bc = (np.array(v, dtype=np.float64, order="C") for v in (a_prev, b_prev, a_curr, b_curr))
     rv = _c(reset_value, np.float64)
@@ -300,7 +300,7 @@ def lyapunov_from_states(prev_states, J: np.ndarray, dt: float):
 
 
 def lle_standard(J: np.ndarray, u0: np.ndarray, dt: float) -> float:
-    """Largest Lyapunov exponent by the normalised vector iteration (Section 4.2.2, eqs. 14-15)."""
+    """Largest Lyapunov exponent by the normalised vector iteration (Section 4.2.2, eqs. 21-22)."""
     J = _c(J, np.float64)
     u0 = _c(u0, np.float64)
     T, d, _ = J.shape
@@ -310,7 +310,7 @@ def lle_standard(J: np.ndarray, u0: np.ndarray, dt: float) -> float:
 
 
 def lle_goom(jac, u0, dt: float, scaled: bool = False) -> float:
-    """Largest Lyapunov exponent as LSE(2 * scan(J_T ... J_1 u_0)) / (2 dt T) (Section 4.2.2, eq. 17):
+    """Largest Lyapunov exponent as LSE(2 * scan(J_T ... J_1 u_0)) / (2 dt T) (Section 4.2.2, eq. 24):
     jac [T, d, d] and u0 [d] are GOOMs; the product is walked by the scan oracle."""
     T, d, _ = np.asarray(jac).shape if not isinstance(jac, tuple) else jac[0].shape
     init = np.asarray(u0).reshape(d, 1)
@@ -321,7 +321,7 @@ def lle_goom(jac, u0, dt: float, scaled: bool = False) -> float:
 
 
 def scaled_exp(z):
-    """Scaled exponentiation of GOOM vectors over the last axis (Section 4.3, eq. 21):
+    """Scaled exponentiation of GOOM vectors over the last axis (Section 4.3, eq. 27):
     returns (scaled reals in [-e^2, e^2], c = max log-magnitude of every vector)."""
     re, sg = _as_working(z)
     d = re.shape[-1]

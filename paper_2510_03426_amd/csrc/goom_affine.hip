@@ -257,7 +257,7 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
         // the state is mantissas 2^eh
         if (out0) pend_goom = float2{C::out_re_f(mine, (float)eh), mine < 0.0f ? C::pi() : 0.0f};
         if (scaled0) {
-            // eq. 21 on the factored vector: with c = log of the largest magnitude, exp(z_i - c + 2) is the
+            // the scaled exponentiation (Section 4.3, eq. 27) on the factored vector: with c = log of the largest magnitude, exp(z_i - c + 2) is the
             // mantissa over the largest mantissa, times e^2; the vector's exponent only enters c
             float am = __builtin_fabsf(mine);
             am = C::template group_allmax<64>(am, am);

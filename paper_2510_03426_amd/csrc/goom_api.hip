@@ -876,7 +876,7 @@ size_t goom_affine_scan_workspace_bytes(int64_t T, int d, int64_t batch, int dty
     return plan_affine(T, d, batch, dtype, opts).total();
 }
 
-// Scaled states (eq. 21) come straight out of the matrix-vector walk where that kernel serves the
+// Scaled states (Section 4.3, eq. 27) come straight out of the matrix-vector walk where that kernel serves the
 // last phase; otherwise the states are written as GOOMs to the workspace and converted.
 static bool affine_scaled_is_fused(const ScanPlan &p, int d, int dtype) { return dtype == GOOM_C64 && (d == 16 || d == 32) && p.C > 1; }
 

@@ -8,7 +8,7 @@
 // without moving.  The left factor A_t is exponentiated block by block (32 of its columns at a time,
 // i.e. 32 values of the contraction index) into a double-buffered LDS tile by all 512 threads, the
 // block after it waiting in registers; the row shifts n_i of A_t
-// (eq. 10: a whole number near the row's largest log2 magnitude) come from a pass of their own over
+// (the identity of Section 3.2, eq. 12, allows any: a whole number near the row's largest log2 magnitude) come from a pass of their own over
 // the input, so a block can be converted before the rest of its rows has been seen.  After the
 // eight blocks of a step the state is renormalised: row shifts folded into the mantissas, one
 // power-of-two exponent per column (double).  A step costs 1024 matrix instructions per wave, which

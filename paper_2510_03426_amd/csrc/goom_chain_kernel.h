@@ -1,9 +1,9 @@
 // Chain kernel: walks a sequence of left factors M_1, M_2, ... and keeps the running
 // product S <- M_t S on chip.  It is the combine of the prefix scan (paper Section 4.1,
-// eq. 9: S'_t = LMME(A'_t, S'_{t-1})) and, with one step, LMME itself (Section 3.2).
+// eq. 14: S'_t = LMME(A'_t, S'_{t-1})) and, with one step, LMME itself (Section 3.2).
 //
-// Each step is the paper's scaled real product (Section 3.2, eq. 7) with two changes that
-// keep what the identity of eq. 10 allows:
+// Each step is the paper's scaled real product (Section 3.2, eq. 10) with two changes that
+// keep what the scaling identity (eq. 12) allows:
 //   * all shifts are whole powers of two, so scaling never rounds;
 //   * the running product is not turned back into logarithms between steps.  It stays a
 //     matrix of real mantissas W with one exponent per column, S[:, k] = W[:, k] 2^e_k
@@ -54,7 +54,7 @@ struct ChainArgs {
     long long init_ngroups; //      entries per group of init_group chunks, init_ngroups groups per batch item
     const unsigned char *bias;
     // linear recurrence with bias, matrix-vector walk only: states in scaled floating-point form
-    // (paper eq. 21) instead of, or besides, GOOMs
+    // (paper Section 4.3, eq. 27) instead of, or besides, GOOMs
     int left_real;       // 1: the left factors are real matrices (component type), not GOOMs (hot float kernel only)
     float *out_scaled;   // NULL or [batch, steps, d]
     float *out_logscale; // NULL or [batch, steps]

@@ -345,7 +345,7 @@ __global__ __launch_bounds__(256) void from_goom_f64_kernel(const double *__rest
     }
 }
 
-// Scaled exponentiation of GOOM vectors (paper Section 4.3, eq. 21): per vector of length d,
+// Scaled exponentiation of GOOM vectors (paper Section 4.3, eq. 27): per vector of length d,
 // c = max of the log-magnitudes, scaled_i = (+-) exp(re_i - c + 2).  A group of G = 2^k >= d
 // lanes (at most 64) owns a vector when d <= 64, so the maximum is a few lane exchanges;
 // longer vectors take a whole wave and several elements per lane.  Evaluated in double and
@@ -438,7 +438,7 @@ template <typename R, typename R2> __global__ __launch_bounds__(256) void scaled
 }
 
 // Signed log-add of two GOOM arrays: the GOOM of exp(x') + exp(y') (paper Section 2, Example 2; the
-// bias step of eq. 20).  In double, rounded once: with m the larger log-magnitude and delta the gap,
+// step that adds the input term in the recurrence over GOOMs, Section 4.3, eq. 26).  In double, rounded once: with m the larger log-magnitude and delta the gap,
 // m + log1p(exp(-delta)) for equal signs, m + log(-expm1(-delta)) for opposite ones.
 // Float components: the same in straight-line code on the short series.  With a the larger log-magnitude,
 // delta = a - b >= 0 and e = exp(-delta): equal signs give a + ln(1 + e), where the ratio for the atanh series is

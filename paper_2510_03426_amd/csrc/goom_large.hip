@@ -1,5 +1,5 @@
 // LMME for shapes beyond the register-resident kernels (any of n, d, m above 128, up to 1024; float
-// components): the same scaled real product (paper Section 3.2, eqs. 7-9; shifts by eq. 10), but as
+// components): the same scaled real product (paper Section 3.2, eqs. 10-11; shifts by the identity of eq. 12), but as
 // separate passes, because a d x d state no longer fits one workgroup and the product is a large
 // dense GEMM that dominates everything else:
 //   1. rows of A' -> reals scaled by the row's power of two (K-contiguous, zero padded);

@@ -1,6 +1,6 @@
 // LMME for shapes above 128 with double components (complex128 GOOMs; the paper's appendix compares
-// LMME on 1024 x 1024 matrices in both formats): the scaled real product of Section 3.2 (eqs. 7-9,
-// shifts by eq. 10) as separate passes through the caller's workspace, like the float path:
+// LMME on 1024 x 1024 matrices in both formats): the scaled real product of Section 3.2 (eqs. 10-11,
+// shifts by the identity of eq. 12) as separate passes through the caller's workspace, like the float path:
 //   1. rows of A' -> reals scaled by the row's power of two (K-contiguous, zero padded);
 //   2. columns of B' -> reals scaled by the column's power of two, written transposed;
 //   3. C~^T = B~^T A~^T on the double-precision matrix instruction (16 x 16 x 4): 128 x 128 tile per

@@ -1,8 +1,8 @@
-// Batched LMME of 128 x 128 x 128 operands (paper Section 3.2, eqs. 7-10), float or double components:
+// Batched LMME of 128 x 128 x 128 operands (paper Section 3.2, eqs. 10-12: the scaled product, its shifts, the scaling identity), float or double components:
 // the inner index is walked in tiles of 32 with a running rescale, so that nothing has to be known
 // about a whole row or column in advance and neither operand is read twice.
 //
-// Eq. 10 lets every row of A' and every column of B' be shifted by any amount.  Here the shifts grow as
+// The scaling identity (eq. 12) lets every row of A' and every column of B' be shifted by any amount.  Here the shifts grow as
 // the tiles arrive: after tile q the accumulators hold the partial product scaled by 2^-(n_i + e_k), with
 // n_i (e_k) a whole number near the largest log2 magnitude seen so far in row i of A' (column k of B').
 // When tile q + 1 raises a maximum, the accumulators of that row (column) are scaled down by the

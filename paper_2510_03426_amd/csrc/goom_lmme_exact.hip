@@ -1,6 +1,6 @@
 // Repair pass of LMME (paper Section 3.2): recompute, by the definition
-//     C'_ik = LSE_j(A'_ij + B'_jk)                                   (eq. 6)
-// every output whose scaled real product (eq. 7, computed by the chain kernel) may have lost
+//     C'_ik = LSE_j(A'_ij + B'_jk)                                   (Section 3.2, eq. 9: the definition)
+// every output whose scaled real product (eq. 10, computed by the chain kernel) may have lost
 // terms to underflow.  The paper itself calls the scaled product a compromise in precision;
 // when the logarithms of the operands spread over hundreds of units, almost every term sits
 // below the component format's range after the row/column shifts and the product comes out

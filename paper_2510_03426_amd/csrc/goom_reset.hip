@@ -14,7 +14,7 @@
 //
 // Per column k a reset removes log R_kk + log(norm of column k) of log-growth from the
 // state; these accumulate (in double) into growth[k], plus the same quantities for the
-// final state, so growth / (dt T) is the Lyapunov spectrum (paper eq. 12, with the
+// final state, so growth / (dt T) is the Lyapunov spectrum (paper Section 4.2.1, eq. 20, with the
 // triangular factors taken at the resets: triangular factors multiply, so their diagonals
 // accumulate exactly as in the step-by-step method).
 //

@@ -592,7 +592,7 @@ def test_largest_lyapunov_exponent(G, oracle, ctype):
             want.append(oracle.lle_goom(Jz, uz, dt, scaled=True))
             std.append(oracle.lle_standard(Jr, u0, dt))
         got = host(G.largest_lyapunov(dev(np.stack(Js)), dt, u0=dev(np.stack(us))))
-        say(f"LLE {np.dtype(ctype).name} T={T} d={d}: gpu {got}, oracle (eq. 17) {np.array(want)}, normalised iteration {np.array(std)}")
+        say(f"LLE {np.dtype(ctype).name} T={T} d={d}: gpu {got}, oracle (eq. 24) {np.array(want)}, normalised iteration {np.array(std)}")
         assert np.abs(got - np.array(want)).max() < 1e-3 and np.abs(got - np.array(std)).max() < 1e-3
         # default start vector: all entries 1 / sqrt(d)
         got0 = host(G.largest_lyapunov(dev(np.stack(Js)), dt))
@@ -611,7 +611,7 @@ def test_largest_lyapunov_exponent(G, oracle, ctype):
 
 @pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
 def test_scaled_exponentiation(G, oracle, ctype):
-    # eq. 21 on states of a recurrence whose magnitudes leave float range, and on ragged shapes
+    # the scaled exponentiation (Section 4.3, eq. 27) on states of a recurrence whose magnitudes leave float range, and on ragged shapes
     comp = np.float32 if ctype == np.complex64 else np.float64
     rng = np.random.default_rng(77)
     for shape in ((3, 1000, 32), (513, 5), (70, 100), (2, 64), (9, 1)):
@@ -653,7 +653,7 @@ def test_scaled_exponentiation(G, oracle, ctype):
     (40, 32, 2, 0, np.complex64, False, 1.05),     # a single chunk
 ])
 def test_affine_scan_scaled_states(G, oracle, T, d, batch, chunk, ctype, ti, gain):
-    # eq. 21 applied to the recurrence's states inside the scan: against the oracle's states, scaled by
+    # the scaled exponentiation (Section 4.3, eq. 27) applied to the recurrence's states inside the scan: against the oracle's states, scaled by
     # the oracle.  An entry is compared where it and its vector's largest entry are well conditioned.
     comp = np.float32 if ctype == np.complex64 else np.float64
     A, b = si.recurrence_inputs(si.BASE_SEED + 57, batch, T, d, gain=gain)

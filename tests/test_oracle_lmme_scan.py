@@ -75,7 +75,7 @@ def test_lmme_exp1000_dot_product_example(oracle):
 
 
 def test_lmme_scaling_identity(oracle):
-    # Section 3.2, eq. 10: shifting rows of A' by r_i and columns of B' by c_k shifts the result
+    # Section 3.2, eq. 12: shifting rows of A' by r_i and columns of B' by c_k shifts the result
     # by r_i + c_k exactly; shifting column j of A' up and row j of B' down changes nothing.
     rng = np.random.default_rng(8)
     n, d, m = 5, 6, 4
@@ -291,7 +291,7 @@ def test_affine_degenerate_cases(oracle):
 
 
 def test_scaled_exponentiation_of_states(oracle):
-    # Section 4.3, eq. 21: c = max Re, scaled = exp(x' - c + 2): values within [-e^2, e^2], the largest
+    # Section 4.3, eq. 27: c = max Re, scaled = exp(x' - c + 2): values within [-e^2, e^2], the largest
     # entry exactly e^2 in magnitude, ratios of entries preserved, a common shift of the logs cancels
     rng = np.random.default_rng(5)
     x = rng.standard_normal((7, 12)) * np.exp(rng.uniform(-30, 30, (7, 12)))

@@ -75,7 +75,7 @@ def test_reset_worked_example_sequential(oracle):
 
 
 def test_reset_tuple_combine_reproduces_appendix_tables(oracle):
-    # The literal (A*, B*) transformation of Section 5, eq. 21, applied in the order of the
+    # The literal (A*, B*) transformation of Section 5, eq. 28, applied in the order of the
     # two tables of Appendix C (right-to-left doubling scan over 4 elements).
     rng = np.random.default_rng(36)
     d = 3
