@@ -18,7 +18,9 @@
  *   - the linear recurrence with bias used for non-diagonal state-space models
  *     (Section 4.3, eqs. 25 and 26);
  *   - sequential QR estimation of Lyapunov spectra (Section 4.2.1, eqs. 19-20) and
- *     the selectively reset recurrence (Section 5; Appendix C).
+ *     the selectively reset recurrence (Section 5; Appendix C);
+ *   - backward passes: the redefined finite derivatives of the codecs (Section 3.1,
+ *     eqs. 5, 6 and 8) and the adjoint recurrence of the linear recurrence with bias.
  *
  * Arithmetic: log-magnitudes are held in IEEE double, signs as one byte (0 = +, 1 = -).
  * Sums of exponentials accumulate in long double.  Codecs evaluate log/exp in
@@ -33,7 +35,9 @@
  * LMME; brute force, the worked scan of Appendix C and the Gaussian growth-rate
  * closed form for the scan; brute force and degenerate cases for the affine
  * recurrence; the Appendix C reset example, S == 0, the log|det| sum rule and the
- * Gaussian closed-form spectrum for the reset recurrence and the QR estimator.
+ * Gaussian closed-form spectrum for the reset recurrence and the QR estimator;
+ * central finite differences of a long-double evaluation over reals, the sum rule of
+ * log-domain gradients and scalar closed forms for the backward passes.
  */
 #include <math.h>
 #include <quadmath.h>
@@ -848,4 +852,101 @@ ORACLE_API void oracle_log_add_exp(const double *xre, const uint8_t *xsg, const 
             osg[i] = sa;
         }
     }
+}
+
+/* ------------------------------------------------------------------------- */
+/* backward passes (Section 3.1: the redefined finite derivatives of the real  */
+/* absolute value, the real logarithm and the complex exponential; Section 3.2:*/
+/* log-scaling constants take no part in gradients; Section 4.3: the recurrence)*/
+/* ------------------------------------------------------------------------- */
+
+/* float -> GOOM, backward: the log-magnitude is log(abs(x)) with d abs(x) / dx := +1 for x >= 0 and -1 for
+ * x < 0 (never zero), and d log(u) / du := 1 / (u + eps) (always finite); so an upstream gradient g with
+ * respect to the log-magnitude gives gx = g * s(x) / (|x| + eps).  The phase is piecewise constant. */
+ORACLE_API void oracle_to_goom_backward(const double *x, const double *g, double *gx, double eps, long n)
+{
+    for (long i = 0; i < n; ++i) {
+        const long double s = x[i] < 0.0 ? -1.0L : 1.0L;
+        gx[i] = (double)((long double)g[i] * s / (fabsl((long double)x[i]) + (long double)eps));
+    }
+}
+
+/* GOOM -> float, backward: x = Re(exp(x')) and d exp(x') / d x' := exp(x') + eps for x >= 0, exp(x') - eps
+ * for x < 0 (never zero); so an upstream gradient gx with respect to x gives, for the log-magnitude,
+ * g = gx * (x + s(x) eps).  Inputs in working form (log-magnitude, sign). */
+ORACLE_API void oracle_from_goom_backward(const double *re, const uint8_t *sg, const double *gx, double *g, double eps, long n)
+{
+    for (long i = 0; i < n; ++i) {
+        const long double mag = expl((long double)re[i]);
+        const long double v = sg[i] ? -mag : mag;
+        g[i] = (double)((long double)gx[i] * (v + (v < 0.0L ? -(long double)eps : (long double)eps)));
+    }
+}
+
+/* Backward pass of h_t = A_t h_{t-1} + b_t over GOOMs, in the limit eps -> 0 of the redefined derivatives (they
+ * differ from the ordinary ones only where a value is within eps of zero; a state entry that is exactly zero
+ * passes no gradient here).  Given the upstream gradients G_t[i] = dL / d Re h'_t[i], the adjoint of the value
+ * h_t[i] receives G_t[i] / h_t[i] directly, and adjoints run backwards through the transposed matrices:
+ *     lam_t = G_t / h_t + A_{t+1}^T lam_{t+1},        lam_{T-1} = G_{T-1} / h_{T-1},
+ * a recurrence of the same kind in reverse time, walked here over GOOMs (the adjoints shrink as fast as the
+ * states grow).  The gradients with respect to log-magnitudes follow with d v / d log|v| = v:
+ *     dL / d Re A'_t[i, j] = lam_t[i] A_t[i, j] h_{t-1}[j],     dL / d Re b'_t[i] = lam_t[i] b_t[i],
+ *     dL / d Re h'_{-1}[j] = h_{-1}[j] sum_i lam_0[i] A_0[i, j]                       (the initial state).
+ * A [T, d, d], b [T, d], h0 [d] or NULL (zero), h [T, d] the forward states, G [T, d] reals.  Outputs: gA
+ * [T, d, d], gb [T, d], gh0 [d] or NULL, and the adjoints themselves as GOOMs lam [T, d]. */
+ORACLE_API void oracle_affine_backward(const double *are, const uint8_t *asg, const double *bre, const uint8_t *bsg,
+                                       const double *h0re, const uint8_t *h0sg, const double *hre, const uint8_t *hsg,
+                                       const double *G, double *gA, double *gb, double *gh0, double *lre, uint8_t *lsg,
+                                       long T, int d)
+{
+    double *z = (double *)malloc(sizeof(double) * (size_t)(d + 1));
+    uint8_t *s = (uint8_t *)malloc((size_t)(d + 1));
+    for (long t = T - 1; t >= 0; --t) {
+        for (int i = 0; i < d; ++i) {
+            int n = 0;
+            const double g = G[(size_t)t * d + i], hr = hre[(size_t)t * d + i];
+            if (g != 0.0 && hr > -INFINITY) {
+                z[n] = log(fabs(g)) - hr;
+                s[n] = (uint8_t)((g < 0.0) ^ hsg[(size_t)t * d + i]);
+                ++n;
+            }
+            if (t + 1 < T) {
+                const double *ar = are + (size_t)(t + 1) * d * d;
+                const uint8_t *as = asg + (size_t)(t + 1) * d * d;
+                for (int j = 0; j < d; ++j) { /* (A_{t+1}^T lam_{t+1})[i] = sum_j A_{t+1}[j, i] lam_{t+1}[j] */
+                    const double a = ar[(size_t)j * d + i], l = lre[(size_t)(t + 1) * d + j];
+                    if (a == -INFINITY || l == -INFINITY) continue;
+                    z[n] = a + l;
+                    s[n] = as[(size_t)j * d + i] ^ lsg[(size_t)(t + 1) * d + j];
+                    ++n;
+                }
+            }
+            signed_lse(n, z, s, &lre[(size_t)t * d + i], &lsg[(size_t)t * d + i], NULL);
+        }
+    }
+    for (long t = 0; t < T; ++t) {
+        for (int i = 0; i < d; ++i) {
+            const double l = lre[(size_t)t * d + i];
+            const uint8_t ls = lsg[(size_t)t * d + i];
+            const double br = bre[(size_t)t * d + i];
+            double v = (l > -INFINITY && br > -INFINITY) ? (double)expl((long double)l + (long double)br) : 0.0;
+            gb[(size_t)t * d + i] = (ls ^ bsg[(size_t)t * d + i]) ? -v : v;
+            for (int j = 0; j < d; ++j) {
+                const double a = are[((size_t)t * d + i) * d + j];
+                const double pr = t > 0 ? hre[(size_t)(t - 1) * d + j] : (h0re ? h0re[j] : -INFINITY);
+                const uint8_t ps = t > 0 ? hsg[(size_t)(t - 1) * d + j] : (h0sg ? h0sg[j] : 0);
+                v = (l > -INFINITY && a > -INFINITY && pr > -INFINITY) ? (double)expl((long double)l + (long double)a + (long double)pr) : 0.0;
+                gA[((size_t)t * d + i) * d + j] = (ls ^ asg[((size_t)t * d + i) * d + j] ^ ps) ? -v : v;
+            }
+        }
+    }
+    if (gh0) {
+        for (int j = 0; j < d; ++j) {
+            long double acc = 0.0L;
+            for (int i = 0; i < d; ++i) acc += (long double)gA[(size_t)i * d + j]; /* lam_0[i] A_0[i, j] h_{-1}[j], summed over i */
+            gh0[j] = h0re ? (double)acc : 0.0;
+        }
+    }
+    free(z);
+    free(s);
 }

@@ -234,6 +234,50 @@ def affine_scan(a, b, h0=None, return_kappa: bool = False):
     return (hre, hsg, kap) if return_kappa else (hre, hsg)
 
 
+def affine_scan_backward(a, b, grad_h, h0=None):
+    """Backward pass of the recurrence h_t = A_t h_{t-1} + b_t over GOOMs (Sections 3.1 and 4.3): given
+    grad_h[..., t, i] = dL / d Re h'_t[i], returns (dL / d Re A', dL / d Re b', dL / d Re h0' or None, adjoints
+    as (re, sg)).  a: [..., T, d, d]; b, grad_h: [..., T, d]."""
+    are, asg = _as_working(a)
+    bre, bsg = _as_working(b)
+    T, d = bre.shape[-2:]
+    lead = bre.shape[:-2]
+    batch = int(np.prod(lead)) if lead else 1
+    hre, hsg = affine_scan(a, b, h0)
+    G = _c(grad_h, np.float64)
+    assert G.shape == lead + (T, d)
+    if h0 is not None:
+        h0re, h0sg = _as_working(h0)
+    gA = np.empty(lead + (T, d, d)); gb = np.empty(lead + (T, d))
+    gh0 = np.empty(lead + (d,)) if h0 is not None else None
+    lre = np.empty(lead + (T, d)); lsg = np.empty(lead + (T, d), dtype=np.uint8)
+    v = lambda x: x.reshape((batch,) + x.shape[len(lead):])
+    for q in range(batch):
+        lib().oracle_affine_backward(_p(v(are)[q]), _p(v(asg)[q]), _p(v(bre)[q]), _p(v(bsg)[q]),
+                                     _p(v(h0re)[q]) if h0 is not None else None, _p(v(h0sg)[q]) if h0 is not None else None,
+                                     _p(v(hre)[q]), _p(v(hsg)[q]), _p(v(G)[q]), _p(v(gA)[q]), _p(v(gb)[q]),
+                                     _p(v(gh0)[q]) if h0 is not None else None, _p(v(lre)[q]), _p(v(lsg)[q]),
+                                     C.c_long(T), C.c_int(d))
+    return gA, gb, gh0, (lre, lsg)
+
+
+def to_goom_backward(x, grad_re, eps: float):
+    """Backward of float -> GOOM with the redefined derivatives of Section 3.1: grad_re * s(x) / (|x| + eps)."""
+    x = _c(x, np.float64); g = _c(grad_re, np.float64)
+    out = np.empty_like(x)
+    lib().oracle_to_goom_backward(_p(x), _p(g), _p(out), C.c_double(eps), C.c_long(x.size))
+    return out
+
+
+def from_goom_backward(z, grad_x, eps: float):
+    """Backward of GOOM -> float with the redefined derivative of Section 3.1: grad_x * (x + s(x) eps)."""
+    re, sg = _as_working(z)
+    g = _c(grad_x, np.float64)
+    out = np.empty_like(re)
+    lib().oracle_from_goom_backward(_p(re), _p(sg), _p(g), _p(out), C.c_double(eps), C.c_long(re.size))
+    return out
+
+
 # --------------------------------------------------------------------------- Lyapunov
 
 def qr(a: np.ndarray):

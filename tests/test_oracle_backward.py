@@ -1,0 +1,118 @@
+"""Pins of the oracle's backward passes (Section 3.1: redefined finite derivatives; Section 4.3: the recurrence)
+against things other than the oracle itself: central finite differences of a long-double evaluation in the
+value domain, closed forms, and the sum rule of log-domain gradients."""
+import math
+
+import numpy as np
+
+import synthetic_inputs as si
+
+
+def goom_of(x):
+    x = np.asarray(x, dtype=np.float64)
+    with np.errstate(divide="ignore"):
+        return np.log(np.abs(x)) + 1j * np.pi * (x < 0)
+
+
+def loss_value_domain(A, b, h0, G):
+    """L = sum_t sum_i G[t, i] log|h_t[i]| with h_t = A_t h_{t-1} + b_t evaluated in long double reals."""
+    h = h0.astype(np.longdouble)
+    L = np.longdouble(0)
+    for t in range(A.shape[0]):
+        h = (A[t].astype(np.longdouble) * h[None, :]).sum(axis=1) + b[t].astype(np.longdouble)
+        L += (G[t].astype(np.longdouble) * np.log(np.abs(h))).sum()
+    return L
+
+
+def test_recurrence_backward_against_finite_differences(oracle):
+    rng = np.random.default_rng(31)
+    T, d = 9, 4
+    A = rng.standard_normal((T, d, d)) * 0.8
+    b = rng.standard_normal((T, d))
+    h0 = rng.standard_normal(d)
+    G = rng.standard_normal((T, d))
+    gA, gb, gh0, _ = oracle.affine_scan_backward(goom_of(A), goom_of(b), G, h0=goom_of(h0))
+    delta = 1e-5
+    # d / d log|v| by scaling v with e^(+-delta)
+    for (t, i, j) in [(0, 0, 0), (3, 1, 2), (8, 3, 3), (5, 2, 0), (1, 3, 1)]:
+        Ap, Am = A.copy(), A.copy()
+        Ap[t, i, j] *= math.exp(delta)
+        Am[t, i, j] *= math.exp(-delta)
+        fd = float((loss_value_domain(Ap, b, h0, G) - loss_value_domain(Am, b, h0, G)) / (2 * delta))
+        assert abs(gA[t, i, j] - fd) < 1e-7 * max(1.0, abs(fd)), (t, i, j, gA[t, i, j], fd)
+    for (t, i) in [(0, 1), (4, 0), (8, 2)]:
+        bp, bm = b.copy(), b.copy()
+        bp[t, i] *= math.exp(delta)
+        bm[t, i] *= math.exp(-delta)
+        fd = float((loss_value_domain(A, bp, h0, G) - loss_value_domain(A, bm, h0, G)) / (2 * delta))
+        assert abs(gb[t, i] - fd) < 1e-7 * max(1.0, abs(fd))
+    for j in range(d):
+        hp, hm = h0.copy(), h0.copy()
+        hp[j] *= math.exp(delta)
+        hm[j] *= math.exp(-delta)
+        fd = float((loss_value_domain(A, b, hp, G) - loss_value_domain(A, b, hm, G)) / (2 * delta))
+        assert abs(gh0[j] - fd) < 1e-7 * max(1.0, abs(fd))
+
+
+def test_recurrence_backward_sum_rule_and_closed_forms(oracle):
+    # scaling all of A_t[i, :] and b_t[i] by e^s scales h_t[i] by e^s for the last step: the log-domain
+    # gradients of a row add up to the adjoint times the state, which at the last step is G itself
+    rng = np.random.default_rng(32)
+    T, d = 40, 6
+    A, b = si.recurrence_inputs(si.BASE_SEED + 80, 1, T, d)
+    A, b = A[0].astype(np.float64) * 3.0, b[0].astype(np.float64)  # states far outside float range need not matter
+    G = rng.standard_normal((T, d))
+    gA, gb, gh0, (lre, lsg) = oracle.affine_scan_backward(goom_of(A), goom_of(b), G)
+    assert gh0 is None
+    assert np.allclose(gA[-1].sum(axis=1) + gb[-1], G[-1], rtol=1e-10, atol=1e-12)
+    hre, hsg = oracle.affine_scan(goom_of(A), goom_of(b))
+    lam_h = np.where(lsg ^ hsg, -1.0, 1.0) * np.exp(lre + hre)  # adjoint times state, step by step
+    assert np.allclose(gA.sum(axis=2) + gb, lam_h, rtol=1e-9, atol=1e-12)
+    # without an initial state the first matrix multiplies a zero vector: no gradient
+    assert np.all(gA[0] == 0.0)
+    # scalar recurrence with a = 0: h_t = b_t, so dL / d log|b_t| = G_t
+    gA1, gb1, _, _ = oracle.affine_scan_backward(goom_of(np.zeros((5, 1, 1))), goom_of(np.array([[2.0], [-3.0], [0.5], [4.0], [-1.0]])),
+                                                 np.array([[1.0], [2.0], [3.0], [4.0], [5.0]]))
+    assert np.allclose(gb1[:, 0], [1, 2, 3, 4, 5]) and np.all(gA1 == 0)
+    # scalar, b = 0, h0 = 1: h_t = a^t, L = sum_t G_t t log a: dL / d log a_s = sum_{t >= s} G_t
+    a = np.full((4, 1, 1), 1.7)
+    Gs = np.array([[1.0], [10.0], [100.0], [1000.0]])
+    gA2, _, gh02, _ = oracle.affine_scan_backward(goom_of(a), goom_of(np.zeros((4, 1))), Gs, h0=goom_of(np.array([1.0])))
+    assert np.allclose(gA2[:, 0, 0], [1111.0, 1110.0, 1100.0, 1000.0]) and np.allclose(gh02, [1111.0])
+
+
+def test_recurrence_backward_far_outside_float_range(oracle):
+    # states of magnitude e^(+-thousands): the adjoints are as small as the states are large, the gradients stay O(G)
+    rng = np.random.default_rng(33)
+    T, d = 300, 5
+    A = goom_of(rng.standard_normal((T, d, d))) + 30.0  # every entry times e^30
+    b = goom_of(rng.standard_normal((T, d)))
+    G = rng.standard_normal((T, d))
+    gA, gb, _, (lre, _) = oracle.affine_scan_backward(A, b, G)
+    hre, _ = oracle.affine_scan(A, b)
+    assert hre.max() > 8000 and lre.min() < -8000
+    assert np.isfinite(gA).all() and np.abs(gA).max() < 1e6
+    assert np.allclose(gA[-1].sum(axis=1) + gb[-1], G[-1], rtol=1e-9, atol=1e-12)
+    # a common shift of all log-magnitudes of A changes no gradient of A (only relative sizes enter)
+    gA2, _, _, _ = oracle.affine_scan_backward(A + 5.0, b + 5.0 * (np.arange(T)[:, None] + 1), G)
+    assert np.allclose(gA2, gA, rtol=1e-6, atol=1e-9)  # (log-magnitudes near 1e4 carry 2e-12 each into the exponentials)
+
+
+def test_codec_backward_redefined_derivatives(oracle):
+    # Section 3.1: d abs(x)/dx := +-1 (never 0, +1 at zero); d log(u)/du := 1/(u + eps); d exp(x')/dx' := exp(x') +- eps
+    eps = 2.0 ** -20
+    x = np.array([2.0, -2.0, 0.0, -0.0, 1e-30, -1e-30, 5.0])
+    g = np.array([1.0, 1.0, 3.0, 3.0, 1.0, 1.0, -2.0])
+    gx = oracle.to_goom_backward(x, g, eps)
+    assert np.allclose(gx, [1 / (2 + eps), -1 / (2 + eps), 3 / eps, 3 / eps, 1 / (1e-30 + eps), -1 / (1e-30 + eps), -2 / (5 + eps)], rtol=1e-15)
+    assert np.all(np.isfinite(gx)) and np.all(gx != 0)
+    # away from zero it is the ordinary derivative of log|x|: central differences
+    for v in (0.3, -7.0, 123.0):
+        fd = (math.log(abs(v * (1 + 1e-6))) - math.log(abs(v * (1 - 1e-6)))) / (2e-6 * v)
+        assert abs(oracle.to_goom_backward(np.array([v]), np.array([1.0]), 0.0)[0] - fd) < 1e-8 * abs(fd)
+    z = np.array([math.log(3.0), math.log(3.0) + 1j * math.pi, -np.inf, -800.0 + 1j * math.pi, 1.5])
+    gz = oracle.from_goom_backward(z, np.array([1.0, 1.0, 2.0, 2.0, -1.0]), eps)
+    want = [3 + eps, -3 - eps, 2 * eps, -2 * eps, -(math.exp(1.5) + eps)]
+    assert np.allclose(gz, want, rtol=1e-14) and np.all(gz != 0)
+    # and the ordinary derivative of +-exp(re) with respect to re when eps = 0
+    assert np.allclose(oracle.from_goom_backward(z[[0, 1, 4]], np.ones(3), 0.0), [3.0, -3.0, math.exp(1.5)], rtol=1e-15)
