@@ -518,7 +518,19 @@ def recurrence(g, torch, dev, si):
         "ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1),
         "hbm_gbs_algorithmic": round(byts / sec / 1e9, 1), "pct_of_hbm_peak": round(100 * byts / sec / 1e9 / HBM_PEAK_GBS, 2),
         "kernels_ms": kernel_times(g, lambda: g.affine_scan(az, bz, out=h))}
-    del h
+    # its backward pass: gradients with respect to the log-magnitudes of A and of the inputs, given those of the states
+    gh = torch.randn((nseq, T, d), device=dev, generator=si.device_generator(251003426 * 10 + 53, dev))
+    fn = lambda: g.affine_scan_backward(az, bz, h, gh)
+    sec = timed(torch, fn, 2)
+    # algorithmic bytes: A read by the transposition, its copy written, read twice by the adjoint scan, A read again and
+    # its gradient (reals) written
+    bbytes = az.numel() * (8 * 5 + 4)
+    res["recurrence_backward_128seq_T65536_d32"] = {
+        "ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1), "hbm_gbs_algorithmic": round(bbytes / sec / 1e9, 1),
+        "kernels_ms": kernel_times(g, fn)}
+    del h, gh
+    g._ws = None
+    torch.cuda.empty_cache()
     # the same recurrence with its states written in scaled floating-point form by the last phase
     sec = timed(torch, lambda: g.affine_scan_scaled(az, bz))
     res["recurrence_scaled_states"] = {"ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1)}

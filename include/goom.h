@@ -334,6 +334,43 @@ int goom_affine_scan_scaled(goom_ctx *ctx, const void *A, const void *bias, cons
 size_t goom_affine_scan_scaled_workspace_bytes(int64_t T, int d, int64_t batch, int dtype,
                                                const goom_scan_opts *opts);
 
+/* ---- backward passes (paper Section 3.1, the redefined finite derivatives; Section 3.2, log-scaling constants
+ *      take no part in gradients; Section 4.3) ------------------------------------------------------------ */
+
+/* Backward of goom_to_goom with respect to the log-magnitudes: the logarithm of a real x is log(abs(x)) with
+ * d abs(x) / dx := +1 for x >= 0, -1 for x < 0 (never zero; paper eq. 5) and d log(u) / du := 1 / (u + eps)
+ * (always finite; eq. 6), so grad_x[i] = grad_re[i] * s(x[i]) / (|x[i]| + eps).  x, grad_re, grad_x: n reals of
+ * the component type (grad_re: gradient with respect to Re y[i]; the phase is piecewise constant and takes no
+ * gradient).  eps >= 0: the paper's data-type-specific small number, left to the caller. */
+int goom_to_goom_backward(goom_ctx *ctx, const void *x, const void *grad_re, void *grad_x, size_t n, int dtype,
+                          double eps);
+
+/* Backward of goom_from_goom: x = Re exp(y) with d exp(y) / dy := exp(y) + eps for x >= 0, exp(y) - eps for
+ * x < 0 (never zero; paper eq. 8), so grad_re[i] = grad_x[i] * (x[i] + s(x[i]) eps), the gradient with respect
+ * to Re y[i].  y: n GOOMs; grad_x, grad_re: n reals of the component type. */
+int goom_from_goom_backward(goom_ctx *ctx, const void *y, const void *grad_x, void *grad_re, size_t n, int dtype,
+                            double eps);
+
+/* Backward of goom_affine_scan (time-varying matrices).  grad_H[b, t, i] = dL / d Re H[b, t, i] for some loss L;
+ * the call returns dL / d Re A[b, t, i, j], dL / d Re bias[b, t, i] and dL / d Re h0[b, j], as reals of the
+ * component type.  The adjoints of the state values, lam_t = grad_H_t / h_t + A_{t+1}^T lam_{t+1}, are a
+ * recurrence of the same kind in reverse time over the transposed matrices; they are computed over GOOMs by the
+ * forward scan on transposed, time-reversed operands (they shrink as fast as the states grow), and
+ *     grad_A[b, t, i, j] = lam_t[i] A_t[i, j] h_{t-1}[j],      grad_bias[b, t, i] = lam_t[i] b_t[i],
+ *     grad_h0[b, j] = h0[j] sum_i lam_0[i] A_0[i, j].
+ * This is the limit eps -> 0 of the paper's redefined derivatives, which differ from the ordinary ones only where
+ * a value lies within eps of zero; a state entry that is exactly zero passes no gradient.
+ * A, bias, h0 (NULL = zero), H: as given to and returned by goom_affine_scan; grad_H: [batch, T, d] reals;
+ * grad_A: [batch, T, d, d] reals; grad_bias: NULL or [batch, T, d] reals; grad_h0: NULL or [batch, d] reals (needs
+ * h0).  opts->flags must be 0.  workspace: goom_affine_scan_backward_workspace_bytes(...) bytes: it holds the
+ * transposed copy of A, so it is a little larger than A itself. */
+int goom_affine_scan_backward(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H,
+                              const void *grad_H, void *grad_A, void *grad_bias, void *grad_h0, int64_t T, int d,
+                              int64_t batch, int dtype, const goom_scan_opts *opts, void *workspace,
+                              size_t workspace_bytes);
+size_t goom_affine_scan_backward_workspace_bytes(int64_t T, int d, int64_t batch, int dtype,
+                                                 const goom_scan_opts *opts);
+
 #pragma GCC visibility pop
 #ifdef __cplusplus
 }

@@ -234,16 +234,16 @@ def affine_scan(a, b, h0=None, return_kappa: bool = False):
     return (hre, hsg, kap) if return_kappa else (hre, hsg)
 
 
-def affine_scan_backward(a, b, grad_h, h0=None):
+def affine_scan_backward(a, b, grad_h, h0=None, h=None):
     """Backward pass of the recurrence h_t = A_t h_{t-1} + b_t over GOOMs (Sections 3.1 and 4.3): given
     grad_h[..., t, i] = dL / d Re h'_t[i], returns (dL / d Re A', dL / d Re b', dL / d Re h0' or None, adjoints
-    as (re, sg)).  a: [..., T, d, d]; b, grad_h: [..., T, d]."""
+    as (re, sg)).  a: [..., T, d, d]; b, grad_h: [..., T, d]; h: the forward states to use (default: computed here)."""
     are, asg = _as_working(a)
     bre, bsg = _as_working(b)
     T, d = bre.shape[-2:]
     lead = bre.shape[:-2]
     batch = int(np.prod(lead)) if lead else 1
-    hre, hsg = affine_scan(a, b, h0)
+    hre, hsg = affine_scan(a, b, h0) if h is None else _as_working(h)
     G = _c(grad_h, np.float64)
     assert G.shape == lead + (T, d)
     if h0 is not None:

@@ -30,6 +30,7 @@ EXPORTS = [
     "goom_largest_lyapunov", "goom_largest_lyapunov_workspace_bytes",
     "goom_affine_scan", "goom_affine_scan_workspace_bytes", "goom_affine_scan_scaled",
     "goom_affine_scan_scaled_workspace_bytes", "goom_scaled_exp", "goom_log_add_exp",
+    "goom_to_goom_backward", "goom_from_goom_backward", "goom_affine_scan_backward", "goom_affine_scan_backward_workspace_bytes",
 ]
 
 
@@ -112,6 +113,11 @@ def load_library():
     lib.goom_affine_scan_scaled.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
     lib.goom_affine_scan_scaled_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_affine_scan_scaled_workspace_bytes.restype = sz
+    lib.goom_to_goom_backward.argtypes = [vp, vp, vp, vp, sz, i32, C.c_double]
+    lib.goom_from_goom_backward.argtypes = [vp, vp, vp, vp, sz, i32, C.c_double]
+    lib.goom_affine_scan_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
+    lib.goom_affine_scan_backward_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
+    lib.goom_affine_scan_backward_workspace_bytes.restype = sz
     _lib = lib
     return lib
 
@@ -429,6 +435,38 @@ class Goom:
         self._check(self.lib.goom_largest_lyapunov(self._ctx, _ptr(jac), _ptr(u0), _ptr(lle), T, d, dt, batch, code,
                                                    C.byref(opts), _ptr(ws), wsn))
         return lle
+
+    def to_goom_backward(self, x, grad_re, eps: float):
+        """grad_re * s(x) / (|x| + eps): backward of to_goom with the paper's redefined derivatives."""
+        out = self.torch.empty_like(x)
+        self._check(self.lib.goom_to_goom_backward(self._ctx, _ptr(x), _ptr(grad_re), _ptr(out), x.numel(), _dtype_code(x), eps))
+        return out
+
+    def from_goom_backward(self, y, grad_x, eps: float):
+        """grad_x * (x + s(x) eps): backward of from_goom with the paper's redefined derivative."""
+        out = self.torch.empty_like(grad_x)
+        self._check(self.lib.goom_from_goom_backward(self._ctx, _ptr(y), _ptr(grad_x), _ptr(out), y.numel(), _dtype_code(y), eps))
+        return out
+
+    def affine_scan_backward(self, a, bias, h, grad_h, h0=None, chunk_len: int = 0):
+        """Gradients of a loss with respect to the log-magnitudes of a, bias (and h0), given grad_h = dL / d Re h."""
+        torch = self.torch
+        code = _dtype_code(a)
+        T, d = bias.shape[-2:]
+        lead = bias.shape[:-2]
+        batch = 1
+        for s in lead:
+            batch *= s
+        comp = torch.float32 if a.dtype == torch.complex64 else torch.float64
+        assert a.shape == lead + (T, d, d) and h.shape == bias.shape and grad_h.shape == bias.shape and grad_h.dtype == comp
+        opts = ScanOpts(chunk_len, 0)
+        ga = torch.empty(lead + (T, d, d), dtype=comp, device=a.device)
+        gb = torch.empty(lead + (T, d), dtype=comp, device=a.device)
+        gh0 = torch.empty(lead + (d,), dtype=comp, device=a.device) if h0 is not None else None
+        ws, wsn = self.workspace(self.lib.goom_affine_scan_backward_workspace_bytes(T, d, batch, code, C.byref(opts)))
+        self._check(self.lib.goom_affine_scan_backward(self._ctx, _ptr(a), _ptr(bias), _ptr(h0), _ptr(h), _ptr(grad_h), _ptr(ga), _ptr(gb),
+                                                       _ptr(gh0), T, d, batch, code, C.byref(opts), _ptr(ws), wsn))
+        return ga, gb, gh0
 
     def scaled_exp(self, z, want_logscale: bool = False):
         """Scaled exponentiation over the last axis: exp(z - max Re z + 2), real."""

@@ -76,6 +76,7 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
 #pragma unroll
     for (int e = 0; e < EPL; ++e) hm[e] = 0.0f;
     double eh = 0.0;
+    bool vec_zero = true; // wave-uniform: every mantissa is zero
     if (a.init_mode == 1) {
         long long iidx = item * a.chunks_per_item + chunk;
         if (a.init_group > 0) {
@@ -103,7 +104,8 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
             }
         }
         // a zero vector carries no meaningful exponent
-        if (__builtin_amdgcn_ballot_w64(nz) == 0 || !(__builtin_fabs(eh) < 1.0e15)) eh = 0.0;
+        vec_zero = __builtin_amdgcn_ballot_w64(nz) == 0;
+        if (vec_zero || !(__builtin_fabs(eh) < 1.0e15)) eh = 0.0;
     }
 
     f4 cur[Q][NV], nxt[Q][NV];
@@ -186,6 +188,15 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
         load_bias(tn, bnxt);
         if (t > 0) store_outputs(t - 1);
         if (!TI) scale_rows(cur);
+        if (vec_zero) {
+            // a zero vector has no scale of its own: it takes the bias's, whatever its magnitude (an adjoint
+            // recurrence starts at e^-1000 and below), instead of flushing the bias on the scale 2^0
+            float m = -__builtin_huge_valf();
+#pragma unroll
+            for (int q = 0; q < Q; ++q) m = C::max_(m, __builtin_fmaf(bcur[q].x, kHi, -nrow[q]));
+            m = C::template group_allmax<64>(m, m);
+            eh = (m > -1.0e30f && m < 1.0e30f) ? (double)__builtin_ceilf(m) : 0.0;
+        }
         const float eh_f = (float)eh;
         float val[Q], barg[Q];
         bool big = false;
@@ -241,6 +252,7 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
             if (row_owner) hvec[q * RPP + rsub] = m;
         }
         eh = all_zero ? 0.0 : eh + (double)down + (double)xm;
+        vec_zero = all_zero;
         // rows to columns through the wave's own LDS words (a wave's LDS operations complete in order)
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -474,7 +486,16 @@ __global__ __launch_bounds__((NW + 1) * 64, 4) void affine_chunk_f64_kernel(Chai
             // b_i enters entry (i, d) of the product, held as accb 2^(n_i + ecol): add (+-) 2^(log2|b_i| - n_i - ecol).
             // Should the column have shrunk so far below the bias that this would overflow, it is scaled down first.
             nrb = nsh[CD::phys(brow)];
-            const float x = (float)__builtin_fma((double)bpre.x, kLog2e, -((double)nrb + ecol)); // -inf for a zero entry or no bias
+            double xd = __builtin_fma((double)bpre.x, kLog2e, -((double)nrb + ecol)); // -inf for a zero entry or no bias
+            if (__builtin_amdgcn_ballot_w64(accb != 0.0) == 0) {
+                // a zero column has no scale of its own: it takes the bias's, whatever its magnitude
+                float m = (float)xd;
+                m = C::template group_allmax<64>(m, m);
+                const double sh = (m > -1.0e30f && m < 1.0e30f) ? (double)__builtin_ceilf(m) : 0.0;
+                ecol += sh;
+                xd -= sh;
+            }
+            const float x = (float)xd;
             float down = 0.0f;
             if (__builtin_amdgcn_ballot_w64(x > 64.0f) != 0) {
                 const float amax = C::template group_allmax<64>(x, x);

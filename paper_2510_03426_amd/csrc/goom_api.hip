@@ -118,7 +118,7 @@ static int check_common(goom_ctx *ctx, int dtype)
 static int need_ctx(goom_ctx *ctx)
 {
     if (!ctx) return fail(nullptr, GOOM_EINVAL, "null context");
-    prof_reset(ctx);
+    if (!ctx->prof_keep) prof_reset(ctx); // (an entry point that calls another one keeps the records so far)
     return check_hip(ctx, hipSetDevice(ctx->device), "hipSetDevice");
 }
 
@@ -1050,6 +1050,84 @@ int goom_affine_scan_scaled(goom_ctx *ctx, const void *A, const void *bias, cons
 {
     if (!scaled) return fail(ctx, GOOM_EINVAL, "null data pointer");
     return run_affine(ctx, A, bias, h0, nullptr, scaled, logscale, T, d, batch, dtype, opts, ws, ws_bytes);
+}
+
+// ---- backward passes ---------------------------------------------------------------------------------------
+struct AffineBackwardPlan {
+    size_t at_bytes, vec_bytes, scan_bytes;
+    size_t total() const { return at_bytes + 2 * vec_bytes + scan_bytes; }
+};
+
+static AffineBackwardPlan plan_affine_backward(long long T, int d, long long batch, int dtype, const goom_scan_opts *opts)
+{
+    AffineBackwardPlan p;
+    const size_t cb = 2 * comp_bytes(dtype);
+    p.at_bytes = align_up((size_t)batch * (size_t)T * d * d * cb, 256);
+    p.vec_bytes = align_up((size_t)batch * (size_t)T * d * cb, 256);
+    p.scan_bytes = align_up(goom_affine_scan_workspace_bytes(T, d, batch, dtype, opts), 256);
+    return p;
+}
+
+size_t goom_affine_scan_backward_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts)
+{
+    if (T <= 0 || d <= 0 || batch <= 0 || d >= GOOM_MAX_DIM) return 0;
+    if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
+    return plan_affine_backward(T, d, batch, dtype, opts).total();
+}
+
+int goom_affine_scan_backward(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *grad_H,
+                              void *grad_A, void *grad_bias, void *grad_h0, int64_t T, int d, int64_t batch, int dtype,
+                              const goom_scan_opts *opts, void *ws, size_t ws_bytes)
+{
+    if (int s = check_scan_args(ctx, A, grad_A, T, d, 1, batch, dtype, opts)) return s;
+    if (!bias || !H || !grad_H) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    if (grad_h0 && !h0) return fail(ctx, GOOM_EINVAL, "a gradient for the initial state needs the initial state");
+    if (d >= GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "the recurrence with bias needs d < %d", GOOM_MAX_DIM);
+    if (!aligned(bias, 16) || !aligned(H, 16) || (h0 && !aligned(h0, 16))) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
+    const size_t rb = comp_bytes(dtype);
+    if (!aligned(grad_H, rb) || !aligned(grad_A, rb) || (grad_bias && !aligned(grad_bias, rb)) || (grad_h0 && !aligned(grad_h0, rb)))
+        return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
+    const AffineBackwardPlan p = plan_affine_backward(T, d, batch, dtype, opts);
+    if (int s = check_workspace(ctx, ws, ws_bytes, p.total())) return s;
+    if (int s = need_ctx(ctx)) return s;
+    unsigned char *w = static_cast<unsigned char *>(ws);
+    void *At = w;
+    void *gt = w + p.at_bytes;
+    void *mu = w + p.at_bytes + p.vec_bytes;
+    void *scan_ws = w + p.at_bytes + 2 * p.vec_bytes;
+    // operands of the adjoint recurrence (transposed matrices in reverse time, G / h as GOOMs) ...
+    if (int s = launch_affine_backward_prepare(ctx, A, H, grad_H, At, gt, T, d, batch, dtype)) return s;
+    // ... the adjoints, by the forward scan itself ...
+    ctx->prof_keep = true;
+    const int st = run_affine(ctx, At, gt, nullptr, mu, nullptr, nullptr, T, d, batch, dtype, opts, p.scan_bytes ? scan_ws : nullptr, p.scan_bytes);
+    ctx->prof_keep = false;
+    if (st) return st;
+    // ... and the gradients
+    return launch_affine_backward_gradients(ctx, A, bias, h0, H, mu, grad_A, grad_bias, grad_h0, T, d, batch, dtype);
+}
+
+int goom_to_goom_backward(goom_ctx *ctx, const void *x, const void *grad_re, void *grad_x, size_t n, int dtype, double eps)
+{
+    if (int s = check_common(ctx, dtype)) return s;
+    if (!(eps >= 0.0)) return fail(ctx, GOOM_EINVAL, "eps must be non-negative");
+    if (n == 0) return ctx ? GOOM_OK : fail(nullptr, GOOM_EINVAL, "null context");
+    if (!x || !grad_re || !grad_x) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    const size_t al = comp_bytes(dtype);
+    if (!aligned(x, al) || !aligned(grad_re, al) || !aligned(grad_x, al)) return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
+    if (int s = need_ctx(ctx)) return s;
+    return launch_to_goom_backward(ctx, x, grad_re, grad_x, n, dtype, eps);
+}
+
+int goom_from_goom_backward(goom_ctx *ctx, const void *y, const void *grad_x, void *grad_re, size_t n, int dtype, double eps)
+{
+    if (int s = check_common(ctx, dtype)) return s;
+    if (!(eps >= 0.0)) return fail(ctx, GOOM_EINVAL, "eps must be non-negative");
+    if (n == 0) return ctx ? GOOM_OK : fail(nullptr, GOOM_EINVAL, "null context");
+    if (!y || !grad_x || !grad_re) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    const size_t al = comp_bytes(dtype);
+    if (!aligned(y, 2 * al) || !aligned(grad_x, al) || !aligned(grad_re, al)) return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
+    if (int s = need_ctx(ctx)) return s;
+    return launch_from_goom_backward(ctx, y, grad_x, grad_re, n, dtype, eps);
 }
 
 size_t goom_scan_reset_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts)

@@ -1,0 +1,281 @@
+// Backward passes (paper Section 3.1: the redefined finite derivatives of the real absolute value, the real
+// logarithm and the complex exponential; Section 4.3: the recurrence h_t = A_t h_{t-1} + b_t over GOOMs).
+//
+// Codecs.  The log-magnitude of a GOOM is log(abs(x)) with d abs / dx := +-1 (+1 at zero, never 0) and
+// d log(u) / du := 1 / (u + eps); the real value of a GOOM is Re exp(x') with d exp(x') / dx' := exp(x') +- eps.
+// Both are one multiply per element around the forward value.
+//
+// Recurrence.  With G_t[i] the gradient of a loss with respect to the log-magnitude of h_t[i], the adjoint of the
+// value h_t[i] is lam_t = G_t / h_t + A_{t+1}^T lam_{t+1}: the same kind of recurrence in reverse time over the
+// transposed matrices, so it runs through the forward scan itself on operands prepared here (matrices transposed
+// and reversed in time, bias G_t / h_t as GOOMs: the adjoints shrink as fast as the states grow, and only their
+// products with states and matrix entries return to ordinary magnitudes).  The gradients with respect to
+// log-magnitudes are lam_t[i] A_t[i, j] h_{t-1}[j] and lam_t[i] b_t[i].
+//
+// A float log-magnitude near 1000 is only good to 6e-5, and the adjoints are signed sums with cancellation, so the
+// adjoint recurrence is not run on the adjoints themselves but on lamhat_t = lam_t e^(c_t), c_t the whole number
+// nearest the largest log-magnitude of h_t: lamhat_t = G_t / (h_t e^(-c_t)) + (e^(c_t - c_{t+1}) A_{t+1}^T) lamhat_{t+1},
+// whose operands all have log-magnitudes of ordinary size (h'_t - c_t is exact in the component type; the matrices
+// move by the whole number c_t - c_{t+1}).  The shift is undone, in double, where the gradients are formed.
+#include "goom_internal.h"
+
+namespace {
+
+constexpr double kInvPi = 0.318309886183790671538;
+
+template <typename R> struct C2;
+template <> struct C2<float> { typedef float2 type; };
+template <> struct C2<double> { typedef double2 type; };
+
+template <typename R> __device__ inline bool odd_phase(R im)
+{
+    const int k = (int)__builtin_rint((double)im * kInvPi);
+    return (k & 1) != 0;
+}
+// e^s for a double sum of log-magnitudes, to the accuracy of the result type: float results take the hardware
+// exponential on the rounded argument (its error, |s| 2^-24, is far inside a gradient's tolerance)
+template <typename R> __device__ inline double exp_for(double s)
+{
+    if (sizeof(R) == 4) return (double)__builtin_amdgcn_exp2f((float)(s * 1.44269504088896340736));
+    return exp(s);
+}
+template <typename R> __device__ inline R pi_of() { return sizeof(R) == 4 ? (R)3.14159274101257324219f : (R)3.14159265358979311600; }
+
+// ---- codecs -----------------------------------------------------------------------------------------------
+template <typename R> __global__ __launch_bounds__(256) void to_goom_backward_kernel(const R *__restrict__ x, const R *__restrict__ g,
+                                                                                     R *__restrict__ gx, size_t n, double eps)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const double v = (double)x[i];
+        const double s = v < 0.0 ? -1.0 : 1.0; // zero counts as non-negative
+        gx[i] = (R)((double)g[i] * s / (__builtin_fabs(v) + eps));
+    }
+}
+
+template <typename R> __global__ __launch_bounds__(256) void from_goom_backward_kernel(const typename C2<R>::type *__restrict__ y,
+                                                                                       const R *__restrict__ gx, R *__restrict__ g, size_t n, double eps)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const typename C2<R>::type z = y[i];
+        const double mag = exp((double)z.x);
+        const double v = odd_phase<R>(z.y) ? -mag : mag;
+        g[i] = (R)((double)gx[i] * (v + (v < 0.0 ? -eps : eps)));
+    }
+}
+
+// ---- recurrence -------------------------------------------------------------------------------------------
+// Operands of the adjoint recurrence, indexed by s = T - 1 - t:
+//   At[b, s] = A[b, T - s]^T for s >= 1 (the matrix for s = 0 multiplies the zero initial adjoint: written as zeros),
+//   gt[b, s, i] = GOOM(G[b, T - 1 - s, i]) - H[b, T - 1 - s, i]   (zero where G is zero or the state is zero).
+// One workgroup per (b, s); the matrix passes through LDS so that both its read and its write are contiguous.
+// c_t: the whole number nearest the largest log-magnitude of h_t (0 for a zero state); every thread of the workgroup
+// returns the same value (red: d-independent scratch of 256 entries)
+template <typename R> __device__ inline R state_scale(const typename C2<R>::type *h, int d, R *red)
+{
+    const R ninf = sizeof(R) == 4 ? (R)-__builtin_huge_valf() : (R)-__builtin_huge_val();
+    R m = ninf;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        const R v = h[i].x;
+        m = v > m ? v : m;
+    }
+    red[threadIdx.x] = m;
+    __syncthreads();
+    for (int sft = 128; sft > 0; sft >>= 1) {
+        if ((int)threadIdx.x < sft) red[threadIdx.x] = red[threadIdx.x + sft] > red[threadIdx.x] ? red[threadIdx.x + sft] : red[threadIdx.x];
+        __syncthreads();
+    }
+    const R top = red[0];
+    __syncthreads();
+    const bool finite = top > ninf && top < -ninf;
+    return finite ? (R)__builtin_rint((double)top) : (R)0;
+}
+
+template <typename R> __global__ __launch_bounds__(256) void bwd_prepare_kernel(const typename C2<R>::type *__restrict__ A,
+                                                                                const typename C2<R>::type *__restrict__ H, const R *__restrict__ G,
+                                                                                typename C2<R>::type *__restrict__ At, typename C2<R>::type *__restrict__ gt,
+                                                                                long long T, int d)
+{
+    typedef typename C2<R>::type c2;
+    extern __shared__ __align__(16) unsigned char smem[];
+    c2 *tile = reinterpret_cast<c2 *>(smem); // [d][d + 1]
+    __shared__ R red[256];
+    const long long b = blockIdx.x / T, s = blockIdx.x % T;
+    const int tid = threadIdx.x;
+    const R ninf = sizeof(R) == 4 ? (R)-__builtin_huge_valf() : (R)-__builtin_huge_val();
+    const long long t = T - 1 - s;
+    const R ct = state_scale<R>(H + (size_t)(b * T + t) * d, d, red);
+    c2 *dst = At + (size_t)(b * T + s) * d * d;
+    if (s == 0) {
+        for (int e = tid; e < d * d; e += 256) dst[e] = c2{ninf, (R)0};
+    } else {
+        const R delta = ct - state_scale<R>(H + (size_t)(b * T + t + 1) * d, d, red); // c_t - c_{t+1}, a whole number
+        const c2 *src = A + (size_t)(b * T + (T - s)) * d * d;
+        for (int e = tid; e < d * d; e += 256) tile[(e / d) * (d + 1) + e % d] = src[e];
+        __syncthreads();
+        for (int e = tid; e < d * d; e += 256) {
+            c2 v = tile[(e % d) * (d + 1) + e / d];
+            v.x += delta; // -inf stays -inf
+            dst[e] = v;
+        }
+    }
+    for (int i = tid; i < d; i += 256) {
+        const R gv = G[(size_t)(b * T + t) * d + i];
+        const c2 h = H[(size_t)(b * T + t) * d + i];
+        c2 o;
+        const bool live = gv != (R)0 && h.x > ninf;
+        o.x = live ? (R)(log(__builtin_fabs((double)gv)) - ((double)h.x - (double)ct)) : ninf;
+        o.y = (live && ((gv < (R)0) != odd_phase<R>(h.y))) ? pi_of<R>() : (R)0;
+        gt[(size_t)(b * T + s) * d + i] = o;
+    }
+}
+
+// Gradients from the scaled adjoints mu[b, s] = lam[b, T - 1 - s] e^(c_{T-1-s}) (GOOMs), one workgroup per (b, t):
+//   gA[b, t, i, j] = lam_t[i] A_t[i, j] h_{t-1}[j],   gb[b, t, i] = lam_t[i] b_t[i].
+// Sums of three log-magnitudes are formed in double (the adjoint and the state are large and opposite).
+template <typename R> __global__ __launch_bounds__(256) void bwd_grad_kernel(const typename C2<R>::type *__restrict__ A,
+                                                                             const typename C2<R>::type *__restrict__ bias,
+                                                                             const typename C2<R>::type *__restrict__ h0,
+                                                                             const typename C2<R>::type *__restrict__ H,
+                                                                             const typename C2<R>::type *__restrict__ mu, R *__restrict__ gA,
+                                                                             R *__restrict__ gb, long long T, int d)
+{
+    typedef typename C2<R>::type c2;
+    extern __shared__ __align__(16) unsigned char smem[];
+    double *lre = reinterpret_cast<double *>(smem); // [d] adjoint log-magnitudes
+    double *pre = lre + d;                          // [d] log-magnitudes of the previous state
+    int *lneg = reinterpret_cast<int *>(pre + d);   // [d]
+    int *pneg = lneg + d;                           // [d]
+    __shared__ R red[256];
+    const long long b = blockIdx.x / T, t = blockIdx.x % T;
+    const int tid = threadIdx.x;
+    const double ninf = -__builtin_huge_val();
+    const double ct = (double)state_scale<R>(H + (size_t)(b * T + t) * d, d, red);
+    for (int i = tid; i < d; i += 256) {
+        const c2 l = mu[(size_t)(b * T + (T - 1 - t)) * d + i];
+        lre[i] = (double)l.x - ct; // -inf stays -inf
+        lneg[i] = odd_phase<R>(l.y) ? 1 : 0;
+        c2 p = c2{(R)ninf, (R)0};
+        if (t > 0) p = H[(size_t)(b * T + t - 1) * d + i];
+        else if (h0) p = h0[(size_t)b * d + i];
+        pre[i] = (double)p.x;
+        pneg[i] = odd_phase<R>(p.y) ? 1 : 0;
+    }
+    __syncthreads();
+    const c2 *ap = A + (size_t)(b * T + t) * d * d;
+    R *op = gA + (size_t)(b * T + t) * d * d;
+    for (int e = tid; e < d * d; e += 256) {
+        const int i = e / d, j = e % d;
+        const c2 a = ap[e];
+        const double s = lre[i] + (double)a.x + pre[j];
+        const bool live = lre[i] > ninf && (double)a.x > ninf && pre[j] > ninf;
+        const double v = live ? exp_for<R>(s) : 0.0;
+        const bool neg = (lneg[i] ^ pneg[j] ^ (odd_phase<R>(a.y) ? 1 : 0)) != 0;
+        op[e] = (R)(neg ? -v : v);
+    }
+    if (gb) {
+        for (int i = tid; i < d; i += 256) {
+            const c2 bb = bias[(size_t)(b * T + t) * d + i];
+            const bool live = lre[i] > ninf && (double)bb.x > ninf;
+            const double v = live ? exp_for<R>(lre[i] + (double)bb.x) : 0.0;
+            const bool neg = (lneg[i] ^ (odd_phase<R>(bb.y) ? 1 : 0)) != 0;
+            gb[(size_t)(b * T + t) * d + i] = (R)(neg ? -v : v);
+        }
+    }
+}
+
+// gh0[b, j] = sum_i gA[b, 0, i, j]   (= h_{-1}[j] sum_i lam_0[i] A_0[i, j]), summed in a fixed order
+template <typename R> __global__ __launch_bounds__(128) void bwd_h0_kernel(const R *__restrict__ gA, R *__restrict__ gh0, long long T, int d)
+{
+    const long long b = blockIdx.x;
+    for (int j = threadIdx.x; j < d; j += 128) {
+        double acc = 0.0;
+        for (int i = 0; i < d; ++i) acc += (double)gA[((size_t)b * T * d + i) * d + j];
+        gh0[(size_t)b * d + j] = (R)acc;
+    }
+}
+
+unsigned blocks_for(size_t n)
+{
+    const size_t b = (n + 255) / 256;
+    return (unsigned)(b < 65536 * 16 ? (b ? b : 1) : 65536 * 16);
+}
+
+} // namespace
+
+namespace goom {
+
+int launch_to_goom_backward(goom_ctx *ctx, const void *x, const void *g, void *gx, size_t n, int dtype, double eps)
+{
+    if (n == 0) return GOOM_OK;
+    prof_begin(ctx, "to_goom_backward");
+    if (dtype == GOOM_C64)
+        hipLaunchKernelGGL(to_goom_backward_kernel<float>, dim3(blocks_for(n)), dim3(256), 0, ctx->stream, static_cast<const float *>(x),
+                           static_cast<const float *>(g), static_cast<float *>(gx), n, eps);
+    else
+        hipLaunchKernelGGL(to_goom_backward_kernel<double>, dim3(blocks_for(n)), dim3(256), 0, ctx->stream, static_cast<const double *>(x),
+                           static_cast<const double *>(g), static_cast<double *>(gx), n, eps);
+    prof_end(ctx);
+    return check_hip(ctx, hipGetLastError(), "launch to_goom_backward");
+}
+
+int launch_from_goom_backward(goom_ctx *ctx, const void *y, const void *gx, void *g, size_t n, int dtype, double eps)
+{
+    if (n == 0) return GOOM_OK;
+    prof_begin(ctx, "from_goom_backward");
+    if (dtype == GOOM_C64)
+        hipLaunchKernelGGL(from_goom_backward_kernel<float>, dim3(blocks_for(n)), dim3(256), 0, ctx->stream, static_cast<const float2 *>(y),
+                           static_cast<const float *>(gx), static_cast<float *>(g), n, eps);
+    else
+        hipLaunchKernelGGL(from_goom_backward_kernel<double>, dim3(blocks_for(n)), dim3(256), 0, ctx->stream, static_cast<const double2 *>(y),
+                           static_cast<const double *>(gx), static_cast<double *>(g), n, eps);
+    prof_end(ctx);
+    return check_hip(ctx, hipGetLastError(), "launch from_goom_backward");
+}
+
+template <typename R> static int bwd_prepare_t(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d, long long batch)
+{
+    typedef typename C2<R>::type c2;
+    const size_t lds = (size_t)d * (d + 1) * sizeof(c2);
+    auto kern = bwd_prepare_kernel<R>;
+    if (lds > 48 * 1024) {
+        if (int s = check_hip(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "hipFuncSetAttribute(bwd_prepare)")) return s;
+    }
+    prof_begin(ctx, "affine_backward_prepare_operands");
+    hipLaunchKernelGGL(kern, dim3((unsigned)(batch * T)), dim3(256), lds, ctx->stream, static_cast<const c2 *>(A), static_cast<const c2 *>(H),
+                       static_cast<const R *>(G), static_cast<c2 *>(At), static_cast<c2 *>(gt), T, d);
+    prof_end(ctx);
+    return check_hip(ctx, hipGetLastError(), "launch bwd_prepare_kernel");
+}
+
+int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d,
+                                   long long batch, int dtype)
+{
+    if (batch * T > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
+    return dtype == GOOM_C64 ? bwd_prepare_t<float>(ctx, A, H, G, At, gt, T, d, batch) : bwd_prepare_t<double>(ctx, A, H, G, At, gt, T, d, batch);
+}
+
+template <typename R> static int bwd_grad_t(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
+                                            void *gb, void *gh0, long long T, int d, long long batch)
+{
+    typedef typename C2<R>::type c2;
+    const size_t lds = (size_t)d * (2 * sizeof(double) + 2 * sizeof(int));
+    prof_begin(ctx, "affine_backward_gradients");
+    hipLaunchKernelGGL(bwd_grad_kernel<R>, dim3((unsigned)(batch * T)), dim3(256), lds, ctx->stream, static_cast<const c2 *>(A),
+                       static_cast<const c2 *>(bias), static_cast<const c2 *>(h0), static_cast<const c2 *>(H), static_cast<const c2 *>(mu),
+                       static_cast<R *>(gA), static_cast<R *>(gb), T, d);
+    if (gh0) hipLaunchKernelGGL(bwd_h0_kernel<R>, dim3((unsigned)batch), dim3(128), 0, ctx->stream, static_cast<const R *>(gA), static_cast<R *>(gh0), T, d);
+    prof_end(ctx);
+    return check_hip(ctx, hipGetLastError(), "launch bwd_grad_kernel");
+}
+
+int launch_affine_backward_gradients(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
+                                     void *gb, void *gh0, long long T, int d, long long batch, int dtype)
+{
+    if (batch * T > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
+    return dtype == GOOM_C64 ? bwd_grad_t<float>(ctx, A, bias, h0, H, mu, gA, gb, gh0, T, d, batch)
+                             : bwd_grad_t<double>(ctx, A, bias, h0, H, mu, gA, gb, gh0, T, d, batch);
+}
+
+} // namespace goom

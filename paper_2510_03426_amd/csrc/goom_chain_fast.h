@@ -328,6 +328,12 @@ __device__ __forceinline__ void chain_body(const ChainArgs &a)
             const float kHi = 1.44269502162933349609375f;
             const float kLo = 1.925963033500011e-8f;
             nrb = nsh[brow];
+            if (__builtin_amdgcn_ballot_w64(accb != 0.0f) == 0) {
+                // a zero column has no scale of its own: it takes the bias's, whatever its magnitude
+                float m = __builtin_fmaf(bpre.x, kHi, -nrb);
+                m = C::template group_allmax<64>(m, m);
+                ecol = (m > -1.0e30f && m < 1.0e30f) ? (double)__builtin_ceilf(m) : 0.0;
+            }
             float x = __builtin_fmaf(bpre.x, kHi, -(nrb + (float)ecol));
             x = __builtin_fmaf(bpre.x, kLo, x);
             float down = 0.0f;

@@ -21,6 +21,7 @@ struct goom_ctx {
     hipStream_t stream;
     std::string last_error;
     bool profile = false;
+    bool prof_keep = false;               // set while one entry point runs another: timing records are not cleared
     std::vector<goom_prof_rec> prof;     // records of the last compute call
     std::vector<goom_prof_rec> prof_pool; // events kept for reuse
     void *scratch = nullptr;              // this device's copy of the library's static scratch array (goom_scan_static)
@@ -154,6 +155,13 @@ int launch_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype)
 int launch_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, size_t n, int dtype);
 int launch_probe(goom_ctx *ctx, const void *a, void *b, size_t bytes, int mode);
 int launch_matrix_probe(goom_ctx *ctx, void *sink, long long iters, int dtype);
+// backward passes (goom_backward.hip)
+int launch_to_goom_backward(goom_ctx *ctx, const void *x, const void *g, void *gx, size_t n, int dtype, double eps);
+int launch_from_goom_backward(goom_ctx *ctx, const void *y, const void *gx, void *g, size_t n, int dtype, double eps);
+int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d,
+                                   long long batch, int dtype);
+int launch_affine_backward_gradients(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
+                                     void *gb, void *gh0, long long T, int d, long long batch, int dtype);
 int launch_widen_goom(goom_ctx *ctx, const void *z64, void *z128, size_t n); // complex64 GOOMs -> complex128 GOOMs
 int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t nvec, int d, int dtype);
 

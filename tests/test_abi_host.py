@@ -67,6 +67,12 @@ def test_argument_validation_without_device(lib):
     assert lib.goom_scan(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), C.c_void_p(0x1010), need) == EINVAL
     assert lib.goom_scan(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), p, need) == EINVAL and "context" in err(lib)
     assert lib.goom_reduce(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), None, 0) == EWS
+    # backward passes
+    assert lib.goom_to_goom_backward(None, p, p, p, 16, 0, C.c_double(-1.0)) == EINVAL and "eps" in err(lib)
+    assert lib.goom_from_goom_backward(None, p, None, p, 16, 0, C.c_double(0.0)) == EINVAL
+    assert lib.goom_affine_scan_backward(None, p, p, None, p, p, p, p, p, 64, 8, 1, 0, None, None, 0) == EINVAL and "initial" in err(lib)
+    assert lib.goom_affine_scan_backward(None, p, p, None, p, p, p, p, None, 64, 8, 1, 0, None, None, 0) == EWS
+    assert lib.goom_affine_scan_backward_workspace_bytes(64, 8, 1, 0, None) > 64 * 8 * 8 * 8
     # the scan on the library's static scratch array: same argument checks, sizes beyond the array refused
     assert lib.goom_scan_static(None, p, None, p, 0, 8, 8, 1, 0, C.byref(o)) == EINVAL and "positive" in err(lib)
     assert lib.goom_scan_static(None, None, None, p, 4, 8, 8, 1, 0, None) == EINVAL

@@ -694,6 +694,73 @@ def test_affine_scan_scaled_states(G, oracle, T, d, batch, chunk, ctype, ti, gai
     assert ratio.max() <= 1
 
 
+# ------------------------------------------------------------------ backward passes (Sections 3.1, 4.3)
+
+@pytest.mark.parametrize("comp", [np.float32, np.float64])
+def test_codec_backward_redefined_derivatives(G, oracle, comp):
+    rng = np.random.default_rng(90)
+    n = (1 << 16) + 7
+    x = (rng.standard_normal(n) * np.exp(rng.uniform(-30, 30, n))).astype(comp)
+    x[:8] = [0.0, -0.0, 1.0, -1.0, 1e-30, -1e-30, 3.0, -3.0]
+    g = rng.standard_normal(n).astype(comp)
+    eps = float(np.finfo(comp).eps)
+    got = host(G.to_goom_backward(dev(x), dev(g), eps)).astype(np.float64)
+    want = oracle.to_goom_backward(x, g, eps)
+    assert np.all(np.abs(got - want) <= 2 * np.finfo(comp).eps * np.abs(want)) and np.all(np.isfinite(got)) and np.all(got[g != 0] != 0)
+    z = oracle.to_goom(x)
+    got = host(G.from_goom_backward(dev(z), dev(g), eps)).astype(np.float64)
+    want = oracle.from_goom_backward(z, g, eps)
+    assert np.all(np.abs(got - want) <= 4 * np.finfo(comp).eps * np.abs(want) + np.finfo(comp).tiny) and np.all(got[g != 0] != 0)
+
+
+@pytest.mark.parametrize("T,d,batch,chunk,ctype,with_h0,gain", [
+    (300, 32, 2, 32, np.complex64, False, 1.05), (1000, 16, 2, 0, np.complex64, True, 1.05), (4000, 32, 1, 0, np.complex64, True, 1.3),
+    (64, 8, 3, 9, np.complex64, True, 1.05), (257, 64, 1, 40, np.complex64, False, 1.05), (200, 16, 2, 16, np.complex128, True, 1.05),
+    (1, 32, 2, 0, np.complex64, True, 1.05)])
+def test_affine_scan_backward(G, oracle, T, d, batch, chunk, ctype, with_h0, gain):
+    """Gradients of L = sum grad_h * Re h with respect to the log-magnitudes of A, bias and h0, against the oracle's
+    adjoint recurrence fed the same forward states."""
+    comp = np.float32 if ctype == np.complex64 else np.float64
+    A, b = si.recurrence_inputs(si.BASE_SEED + 91, batch, T, d, gain=gain)
+    Az, bz = oracle.to_goom(A.astype(comp)), oracle.to_goom(b.astype(comp))
+    h0 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 92, 9, batch * d).reshape(batch, d).astype(comp)) if with_h0 else None
+    Gh = si.normal_f32(si.BASE_SEED + 93, 10, batch * T * d).reshape(batch, T, d).astype(comp)
+    say(f"affine backward T={T} d={d} batch={batch} chunk={chunk} {np.dtype(ctype).name} h0={with_h0}")
+    Hd = G.affine_scan(dev(Az), dev(bz), None if h0 is None else dev(h0), chunk_len=chunk)
+    H = host(Hd)
+    ga, gb, gh0 = G.affine_scan_backward(dev(Az), dev(bz), Hd, dev(Gh), None if h0 is None else dev(h0), chunk_len=chunk)
+    ga, gb = host(ga).astype(np.float64), host(gb).astype(np.float64)
+    wa, wb, wh0, (lre, lsg) = oracle.affine_scan_backward(Az, bz, Gh, h0=h0, h=H)
+    if gain > 1.2:
+        assert H.real.max() > 700 and lre.min() < -700  # states and adjoints far outside float range, gradients not
+    # conditioning, decided by the oracle alone: the adjoints are signed sums; where half-unit perturbations of the
+    # inputs' log-magnitudes move a gradient by more than 1/16 of the tolerance the entry is left out
+    rng = np.random.default_rng(5)
+    eta = 2.0 ** -24 if comp == np.float32 else 2.0 ** -53
+    rel = 1e-3 if comp == np.float32 else 1e-9
+    tol_a = rel * np.abs(wa) + 1e-3 * rel * np.abs(wa).max(axis=(-1, -2), keepdims=True) + float(np.finfo(comp).tiny)  # (results are reals of the component type)
+    tol_b = rel * np.abs(wb) + 1e-3 * rel * np.abs(wb).max(axis=-1, keepdims=True) + float(np.finfo(comp).tiny)
+    sens_a, sens_b = np.zeros_like(wa), np.zeros_like(wb)
+    for _ in range(2):
+        pert = lambda z: None if z is None else (z.astype(np.complex128) + eta * rng.standard_normal(z.shape) * np.where(np.isfinite(z.real), 1.0, 0.0))
+        pa, pb, _, _ = oracle.affine_scan_backward(pert(Az), pert(bz), Gh, h0=pert(h0), h=pert(H))
+        sens_a, sens_b = np.maximum(sens_a, np.abs(pa - wa)), np.maximum(sens_b, np.abs(pb - wb))
+    well_a, well_b = sens_a <= tol_a / 16, sens_b <= tol_b / 16
+    ra = (np.abs(ga - wa) / tol_a)[well_a].max()
+    rb = (np.abs(gb - wb) / tol_b)[well_b].max()
+    say(f"  worst error / tolerance: grad A {ra:.3g}, grad bias {rb:.3g}; left out as ill conditioned {1 - well_a.mean():.2e} / {1 - well_b.mean():.2e}")
+    # (an expansive recurrence makes a quarter of its adjoints cancelling sums; the logs print the share)
+    min_well = 0.7 if gain > 1.2 else 0.9
+    assert ra <= 1 and rb <= 1 and well_a.mean() > min_well and well_b.mean() > min_well
+    sig = well_a & (np.abs(wa) > 2 * tol_a)  # signs wherever the tolerance does not reach zero
+    assert np.array_equal(np.signbit(ga)[sig], np.signbit(wa)[sig])
+    if with_h0:
+        gh0 = host(gh0).astype(np.float64)
+        assert np.all(np.abs(gh0 - wh0) <= 2e-3 * np.abs(wh0) + 1e-4 * np.abs(wh0).max())
+    else:
+        assert np.all(ga[:, 0] == 0)  # the first matrix multiplies a zero vector
+
+
 @pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
 def test_signed_log_add(G, oracle, ctype):
     comp = np.float32 if ctype == np.complex64 else np.float64
