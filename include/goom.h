@@ -135,6 +135,11 @@ int goom_to_goom(goom_ctx *ctx, const void *x, void *y, size_t n, int dtype, uin
  * (paper Section 3.1, eq. 7); overflow gives +-inf, underflow +-0. */
 int goom_from_goom(goom_ctx *ctx, const void *y, void *x, size_t n, int dtype);
 
+/* Number of entries of a GOOM array whose log-magnitude is +inf or NaN (-inf, the GOOM of zero, is finite): the
+ * paper's notion of a failed chain is one that ends in non-finite values (Section 4.1).  z: n GOOMs; count: one
+ * device uint64, overwritten.  Reads z once; an optional check after any of the product calls. */
+int goom_count_nonfinite(goom_ctx *ctx, const void *z, size_t n, int dtype, uint64_t *count);
+
 /* ---- LMME (paper Section 3.2) ---------------------------------------------------- */
 
 /* C[b] = LMME(A[b], B[b]) = log(exp(A[b]) exp(B[b])) for b < batch.

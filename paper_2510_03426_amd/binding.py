@@ -30,7 +30,7 @@ EXPORTS = [
     "goom_largest_lyapunov", "goom_largest_lyapunov_workspace_bytes",
     "goom_affine_scan", "goom_affine_scan_workspace_bytes", "goom_affine_scan_scaled",
     "goom_affine_scan_scaled_workspace_bytes", "goom_scaled_exp", "goom_log_add_exp",
-    "goom_to_goom_backward", "goom_from_goom_backward", "goom_affine_scan_backward", "goom_affine_scan_backward_workspace_bytes",
+    "goom_count_nonfinite", "goom_to_goom_backward", "goom_from_goom_backward", "goom_affine_scan_backward", "goom_affine_scan_backward_workspace_bytes",
 ]
 
 
@@ -113,6 +113,7 @@ def load_library():
     lib.goom_affine_scan_scaled.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
     lib.goom_affine_scan_scaled_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_affine_scan_scaled_workspace_bytes.restype = sz
+    lib.goom_count_nonfinite.argtypes = [vp, vp, sz, i32, vp]
     lib.goom_to_goom_backward.argtypes = [vp, vp, vp, vp, sz, i32, C.c_double]
     lib.goom_from_goom_backward.argtypes = [vp, vp, vp, vp, sz, i32, C.c_double]
     lib.goom_affine_scan_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
@@ -435,6 +436,12 @@ class Goom:
         self._check(self.lib.goom_largest_lyapunov(self._ctx, _ptr(jac), _ptr(u0), _ptr(lle), T, d, dt, batch, code,
                                                    C.byref(opts), _ptr(ws), wsn))
         return lle
+
+    def count_nonfinite(self, z) -> int:
+        """Entries of a GOOM tensor whose log-magnitude is +inf or NaN (synchronises to return the number)."""
+        cnt = self.torch.zeros(1, dtype=self.torch.int64, device=z.device)
+        self._check(self.lib.goom_count_nonfinite(self._ctx, _ptr(z), z.numel(), _dtype_code(z), _ptr(cnt)))
+        return int(cnt.item())
 
     def to_goom_backward(self, x, grad_re, eps: float):
         """grad_re * s(x) / (|x| + eps): backward of to_goom with the paper's redefined derivatives."""

@@ -871,7 +871,7 @@ static AffinePlan plan_affine(long long T, int d, long long batch, int dtype, co
 
 size_t goom_affine_scan_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts)
 {
-    if (T <= 0 || d <= 0 || batch <= 0 || d >= GOOM_MAX_DIM) return 0;
+    if (T <= 0 || d <= 0 || batch <= 0 || d > GOOM_MAX_DIM) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
     return plan_affine(T, d, batch, dtype, opts).total();
 }
@@ -887,7 +887,7 @@ static size_t affine_states_bytes(long long T, int d, long long batch, int dtype
 
 size_t goom_affine_scan_scaled_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts)
 {
-    if (T <= 0 || d <= 0 || batch <= 0 || d >= GOOM_MAX_DIM) return 0;
+    if (T <= 0 || d <= 0 || batch <= 0 || d > GOOM_MAX_DIM) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
     const AffinePlan ap = plan_affine(T, d, batch, dtype, opts);
     return align_up(ap.total(), 256) + (affine_scaled_is_fused(ap.p, d, dtype) ? 0 : affine_states_bytes(T, d, batch, dtype));
@@ -902,7 +902,7 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
     const bool want_scaled = H == nullptr;
     if (int s = check_scan_args(ctx, A, want_scaled ? scaled : H, T, d, 1, batch, dtype, &plain)) return s;
     if (!bias) return fail(ctx, GOOM_EINVAL, "null data pointer");
-    if (d >= GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "the recurrence with bias needs d < %d", GOOM_MAX_DIM);
+    if (d > GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "the recurrence with bias needs d <= %d", GOOM_MAX_DIM);
     if (!aligned(bias, 16) || (h0 && !aligned(h0, 16))) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
     if (logscale && !aligned(logscale, comp_bytes(dtype))) return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
     const AffinePlan ap = plan_affine(T, d, batch, dtype, opts);
@@ -1070,7 +1070,7 @@ static AffineBackwardPlan plan_affine_backward(long long T, int d, long long bat
 
 size_t goom_affine_scan_backward_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts)
 {
-    if (T <= 0 || d <= 0 || batch <= 0 || d >= GOOM_MAX_DIM) return 0;
+    if (T <= 0 || d <= 0 || batch <= 0 || d > GOOM_MAX_DIM) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
     return plan_affine_backward(T, d, batch, dtype, opts).total();
 }
@@ -1082,7 +1082,7 @@ int goom_affine_scan_backward(goom_ctx *ctx, const void *A, const void *bias, co
     if (int s = check_scan_args(ctx, A, grad_A, T, d, 1, batch, dtype, opts)) return s;
     if (!bias || !H || !grad_H) return fail(ctx, GOOM_EINVAL, "null data pointer");
     if (grad_h0 && !h0) return fail(ctx, GOOM_EINVAL, "a gradient for the initial state needs the initial state");
-    if (d >= GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "the recurrence with bias needs d < %d", GOOM_MAX_DIM);
+    if (d > GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "the recurrence with bias needs d <= %d", GOOM_MAX_DIM);
     if (!aligned(bias, 16) || !aligned(H, 16) || (h0 && !aligned(h0, 16))) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
     const size_t rb = comp_bytes(dtype);
     if (!aligned(grad_H, rb) || !aligned(grad_A, rb) || (grad_bias && !aligned(grad_bias, rb)) || (grad_h0 && !aligned(grad_h0, rb)))
@@ -1152,6 +1152,15 @@ int goom_lyapunov_spectrum(goom_ctx *ctx, const void *J, const void *S0, void *s
     if (!(dt > 0.0)) return fail(ctx, GOOM_EINVAL, "dt must be positive");
     return run_reset(ctx, J, S0, states, nullptr, lambda, 1.0 / (dt * (double)T), T, d, batch, dtype, opts, workspace,
                      workspace_bytes);
+}
+
+int goom_count_nonfinite(goom_ctx *ctx, const void *z, size_t n, int dtype, uint64_t *count)
+{
+    if (int s = check_common(ctx, dtype)) return s;
+    if (!count || (n > 0 && !z)) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    if (!aligned(count, 8) || !aligned(z, 2 * comp_bytes(dtype))) return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
+    if (int s = need_ctx(ctx)) return s;
+    return launch_count_nonfinite(ctx, z, n, dtype, reinterpret_cast<unsigned long long *>(count));
 }
 
 int goom_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, size_t n, int dtype)

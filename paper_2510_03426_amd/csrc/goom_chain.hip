@@ -25,7 +25,7 @@ static int pick_waves(int dp, int nslabs)
     const int kt = dp / 16;
     if (nslabs <= 1) return 1;
     if (nslabs <= kt) return kt;
-    if (nslabs == kt + 1 && dp != 128) return kt + 1;
+    if (nslabs == kt + 1) return kt + 1;
     return -1;
 }
 

@@ -337,7 +337,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr size_t kTileBytes = (size_t)DP * LDA * sizeof(R);
     constexpr size_t kBufBytes = kTileBytes + (size_t)DP * sizeof(double);
-    constexpr int NBUF = (2 * kBufBytes + 64 <= 160 * 1024) ? 2 : 1; // double buffer when it fits in LDS
+    constexpr int NBUF = (2 * kBufBytes + 128 <= 160 * 1024) ? 2 : 1; // double buffer when it fits in LDS
     // buffer b: tile at smem + b * kBufBytes, row shifts after the tile
     auto tile_of = [&](int b) { return reinterpret_cast<R *>(smem + (size_t)b * kBufBytes); };
     auto nsh_of = [&](int b) { return reinterpret_cast<R *>(smem + (size_t)b * kBufBytes + kTileBytes); };
@@ -794,8 +794,8 @@ template <typename R, int DP, int NW, int LEFT_FACT, bool FAST, typename IO = R>
 {
     constexpr int LDA = DP + Comp<R>::kPad;
     const size_t buf = (size_t)DP * LDA * sizeof(R) + (size_t)DP * sizeof(double);
-    const int nbuf = (2 * buf + 64 <= 160 * 1024) ? 2 : 1;
-    size_t lds = nbuf * buf + 64;
+    const int nbuf = (2 * buf + 128 <= 160 * 1024) ? 2 : 1;
+    size_t lds = nbuf * buf + 128;
     auto kern = chain_kernel<R, DP, NW, LEFT_FACT, FAST, IO>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -826,6 +826,7 @@ template <typename R, int LEFT_FACT, typename IO = R> int dispatch(goom_ctx *ctx
     GOOM_CASE(64, 5)
     GOOM_CASE(128, 1)
     GOOM_CASE(128, 8)
+    GOOM_CASE(128, 9)
 #undef GOOM_CASE
     return goom::fail(ctx, GOOM_EUNSUPPORTED, "no kernel for padded size %d with %d waves", dp, nw);
 }

@@ -591,6 +591,36 @@ int launch_widen_goom(goom_ctx *ctx, const void *z64, void *z128, size_t n)
     return check_hip(ctx, hipGetLastError(), "launch widen_goom");
 }
 
+// Entries of a GOOM array whose log-magnitude is +inf or NaN (-inf is the GOOM of zero and counts as finite): the
+// paper's one failure notion, a chain that ends in "catastrophic numerical error" (Section 4.1).  Per-wave counts
+// are added to the caller's counter with integer atomics (the sum does not depend on their order).
+template <typename R2> __global__ __launch_bounds__(256) void count_nonfinite_kernel(const R2 *__restrict__ z, size_t n, unsigned long long *count)
+{
+    unsigned long long mine = 0;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const auto re = z[i].x;
+        mine += (re != re || re == (decltype(re))__builtin_huge_val()) ? 1ull : 0ull; // NaN or +inf
+    }
+    for (int sft = 32; sft > 0; sft >>= 1) mine += __shfl_xor(mine, sft, 64);
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(count, mine);
+}
+
+__global__ void zero_counter_kernel(unsigned long long *count) { *count = 0ull; }
+
+int launch_count_nonfinite(goom_ctx *ctx, const void *z, size_t n, int dtype, unsigned long long *count)
+{
+    hipLaunchKernelGGL(zero_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, count);
+    if (n == 0) return check_hip(ctx, hipGetLastError(), "launch zero_counter");
+    prof_begin(ctx, "count_nonfinite");
+    if (dtype == GOOM_C64)
+        hipLaunchKernelGGL(count_nonfinite_kernel<float2>, dim3(grid_for(n)), dim3(256), 0, ctx->stream, static_cast<const float2 *>(z), n, count);
+    else
+        hipLaunchKernelGGL(count_nonfinite_kernel<double2>, dim3(grid_for(n)), dim3(256), 0, ctx->stream, static_cast<const double2 *>(z), n, count);
+    prof_end(ctx);
+    return check_hip(ctx, hipGetLastError(), "launch count_nonfinite");
+}
+
 int launch_log_add_exp(goom_ctx *ctx, const void *x, const void *y, void *out, size_t n, int dtype)
 {
     if (n == 0) return GOOM_OK;

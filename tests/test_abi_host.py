@@ -93,7 +93,8 @@ def test_argument_validation_without_device(lib):
     assert lib.goom_lmme(None, p, p, p, 1, 8, 8, 8, 0, 2, None, 0) == EINVAL
     # affine
     assert lib.goom_affine_scan(None, p, None, None, p, 4, 8, 1, 0, None, None, 0) == EINVAL
-    assert lib.goom_affine_scan(None, p, p, None, p, 4, 128, 1, 0, None, None, 0) == EUNSUP
+    assert lib.goom_affine_scan(None, p, p, None, p, 4, 129, 1, 0, None, None, 0) == EUNSUP
+    assert lib.goom_affine_scan(None, p, p, None, p, 400, 128, 1, 0, None, None, 0) == EWS  # the largest size of the recurrence
     assert lib.goom_affine_scan(None, p, p, None, None, 4, 8, 1, 0, None, None, 0) == EINVAL
     assert lib.goom_affine_scan_scaled(None, p, p, None, None, None, 4, 8, 1, 0, None, None, 0) == EINVAL
     assert lib.goom_affine_scan_scaled(None, p, p, None, p, None, 4, 8, 1, 0, None, None, 0) == EWS

@@ -153,6 +153,21 @@ def test_codecs_bit_exact(G, oracle, comp):
     assert G.to_goom(torch.empty(0, dtype=torch.float32, device="cuda")).numel() == 0
 
 
+def test_count_nonfinite(G, oracle):
+    # the paper's failure notion (Section 4.1): a chain fails when its states stop being finite; zeros (-inf) are fine
+    rng = np.random.default_rng(7)
+    for ctype in (np.complex64, np.complex128):
+        z = (rng.normal(0, 50, (1 << 18) + 5) + 1j * np.pi * rng.integers(0, 2, (1 << 18) + 5)).astype(ctype)
+        z[::1000] = -np.inf
+        assert G.count_nonfinite(dev(z)) == 0
+        z[5], z[77], z[-1] = np.inf, np.nan, np.inf + 1j * np.pi
+        assert G.count_nonfinite(dev(z)) == 3
+    # a float32 real chain overflows where the GOOM chain does not
+    x = si.normal_chain(si.BASE_SEED + 1, 400, 64)
+    P = G.scan(G.to_goom(dev(x)))
+    assert G.count_nonfinite(P) == 0 and host(P).real.max() > 700
+
+
 def test_decode_accepts_any_phase_multiple(G, oracle):
     z = np.array([3 + 2j * math.pi, 3 + 4j * math.pi, 3 + 1j * math.pi, 3 - 3j * math.pi, -np.inf + 0j, 200 + 0j],
                  dtype=np.complex64)
@@ -409,7 +424,7 @@ def test_scan_beyond_float_range(G, oracle):
 # ------------------------------------------------------------------------------ affine
 
 @pytest.mark.parametrize("T,d,batch,chunk", [(64, 8, 2, 0), (300, 32, 3, 32), (100, 16, 1, 9), (1, 32, 2, 0), (257, 64, 1, 40),
-                                             (1000, 32, 2, 5)])
+                                             (1000, 32, 2, 5), (90, 128, 2, 16), (70, 100, 1, 0)])
 def test_affine_scan_matches_oracle(G, oracle, T, d, batch, chunk):
     A, b = si.recurrence_inputs(si.BASE_SEED + 50, batch, T, d)
     Az, bz = oracle.to_goom(A), oracle.to_goom(b)
