@@ -329,6 +329,55 @@ def reset_combine_real(a_prev, b_prev, a_curr, b_curr, select_prev: bool, reset_
     return ap, bp, ac, bc
 
 
+def reset_scan_tree_real(x0, a, policy: int = 0, cos_threshold: float = 0.99):
+    """The selective-resetting scan of Section 5 in the order of the paper's parallel prefix scan (Appendix C), over
+    plain real matrices with the literal tuple transformation (eq. 28).  Elements: (X_0, 0), (A_1, 0), ..., (A_T, 0).
+    Parallel step k works on blocks of 2^k elements: every element of a block's upper half is updated from the last
+    element of its lower half.  Before each parallel step every element whose transition slot is selected and whose
+    bias slot is all zeros is reset in place (B* <- R(A*), A* <- 0), as in the appendix's second table.  S: any two
+    columns with |cosine| above the threshold (policy 0), always (1), never (-1); R: unit columns, then the
+    orthonormal factor of a QR with positive diagonal (Section 4.2.1 (a)).
+    x0: [d, d]; a: [T, d, d] reals.  Returns (sums [T + 1, d, d] = A* + B* per element, was_reset [T + 1])."""
+    x0 = _c(x0, np.float64)
+    a = _c(a, np.float64)
+    T, d, _ = a.shape
+    n = T + 1
+    As = [x0.copy()] + [a[t].copy() for t in range(T)]
+    Bs = [np.zeros((d, d)) for _ in range(n)]
+    zero = np.zeros((d, d))
+
+    def selected(m):
+        if policy == 1:
+            return True
+        if policy == -1:
+            return False
+        nrm = np.sqrt((m * m).sum(axis=0))
+        if np.any(nrm == 0.0):
+            return False
+        g = (m / nrm).T @ (m / nrm)
+        return bool(np.any(np.abs(g[np.triu_indices(d, 1)]) > cos_threshold))
+
+    def reset_value(m):
+        nrm = np.sqrt((m * m).sum(axis=0))
+        q, _ = qr(m / np.where(nrm > 0, nrm, 1.0))
+        return q
+
+    half = 1
+    while half < n:
+        for i in range(n):  # selective reset, in place
+            if not Bs[i].any() and As[i].any() and selected(As[i]):
+                Bs[i] = reset_value(As[i])
+                As[i] = zero.copy()
+        for i in range(n):  # ordinary recurrence with bias: upper half of every block from the lower half's last element
+            if i & half:
+                j = (i & ~(half - 1) & ~half) + half - 1
+                _, _, As[i], Bs[i] = reset_combine_real(As[j], Bs[j], As[i], Bs[i], False, zero)
+        half *= 2
+    sums = np.stack([x + y for x, y in zip(As, Bs)])
+    was_reset = np.array([bool(y.any()) for y in Bs])
+    return sums, was_reset
+
+
 def lyapunov_from_states(prev_states, J: np.ndarray, dt: float):
     """Groups (b)-(d) of Section 4.2.1: prev_states = (re, sg) of S_0 .. S_{T-1} (working form),
     J the real Jacobians [T, d, d].  Returns (lambda [d], per-step log|diag R| [T, d])."""

@@ -113,6 +113,41 @@ def test_reset_tuple_combine_reproduces_appendix_tables(oracle):
     assert not np.allclose(b, A3 @ A2 @ B2 + B3)
 
 
+def test_reset_scan_in_tree_order(oracle):
+    # the whole scan in the paper's parallel order (Appendix C), literal tuples over reals
+    rng = np.random.default_rng(37)
+    d, T = 3, 11
+    A = rng.standard_normal((T, d, d))
+    X0 = rng.standard_normal((d, d))
+    # S == 0: the plain recurrence, every bias slot stays zero
+    sums, was = oracle.reset_scan_tree_real(X0, A, policy=-1)
+    want = [X0]
+    for t in range(T):
+        want.append(A[t] @ want[-1])
+    assert not was.any() and np.allclose(sums, np.stack(want), rtol=1e-12, atol=1e-13)
+    # S == 1: every element is reset before the first parallel step, and a reset element ignores what precedes it
+    sums, was = oracle.reset_scan_tree_real(X0, A, policy=1)
+    assert was.all()
+    for i, m in enumerate([X0] + list(A)):
+        assert np.allclose(sums[i], numpy_reset(m), rtol=1e-10, atol=1e-12)
+    # the appendix's second table: four elements, the compound A_1 X_0 selected (nearly parallel columns) and nothing
+    # else: outputs X_0, R(A_1 X_0), A_2 R(A_1 X_0), A_3 A_2 R(A_1 X_0)
+    def max_cos(m):
+        n = m / np.linalg.norm(m, axis=0, keepdims=True)
+        return np.abs((n.T @ n)[np.triu_indices(m.shape[0], 1)]).max()
+    M = rng.standard_normal((d, d))
+    M[:, 2] = M[:, 0] + 1e-6 * rng.standard_normal(d)  # the compound A_1 X_0: two nearly parallel columns
+    A1 = M @ np.linalg.inv(X0)
+    A2, A3 = rng.standard_normal((d, d)), rng.standard_normal((d, d))
+    c = A1 @ X0
+    assert max_cos(c) > 0.999999 and max(max_cos(m) for m in (X0, A1, A2, A3, A3 @ A2)) < 0.99
+    sums, was = oracle.reset_scan_tree_real(X0, np.stack([A1, A2, A3]), policy=0, cos_threshold=0.999)
+    r1 = numpy_reset(c)
+    assert was.tolist() == [False, True, True, True]
+    for got, want in zip(sums, (X0, r1, A2 @ r1, A3 @ A2 @ r1)):
+        assert np.allclose(got, want, rtol=1e-9, atol=1e-11)
+
+
 def test_reset_growth_equals_qr_spectrum(oracle):
     # triangular factors multiply, so the log-growth removed at resets (plus the final
     # factorisation) gives the same spectrum as QR at every step
