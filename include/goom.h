@@ -260,6 +260,22 @@ int goom_scan_reset(goom_ctx *ctx, const void *J, const void *S0, void *states,
 size_t goom_scan_reset_workspace_bytes(int64_t T, int d, int64_t batch, int dtype,
                                        const goom_reset_opts *opts);
 
+/* The same recurrence with the selective-resetting transformation applied in the order of the paper's own
+ * parallel prefix scan (Section 5, eq. 28; Appendix C): elements (X_0, J_0, ..., J_{T-1}); parallel step k updates
+ * the upper half of every block of 2^k elements from the last element of its lower half; before every parallel
+ * step each interim compound that S selects (opts->policy, opts->cos_threshold; chunk_len is not used) and that
+ * has not been reset yet is replaced by R of itself and from then on ignores what precedes it.  Which compounds
+ * exist depends on this order, so the result differs from goom_scan_reset's (both are instances of the paper's
+ * method); a compound that does not contain X_0 carries no history, and resetting it discards the earlier
+ * states' subspaces, which is why goom_scan_reset, not this call, serves the spectrum estimators.  O(T log T)
+ * products.  states: [batch, T, d, d] (the paper's "Sums"); reset_flags: NULL or [batch, T] bytes, 1 where the
+ * final value of a state descends from a reset.  Both formats, d <= 64.
+ * workspace: goom_scan_reset_tree_workspace_bytes(...) bytes. */
+int goom_scan_reset_tree(goom_ctx *ctx, const void *J, const void *S0, void *states, uint8_t *reset_flags,
+                         int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts, void *workspace,
+                         size_t workspace_bytes);
+size_t goom_scan_reset_tree_workspace_bytes(int64_t T, int d, int64_t batch, int dtype);
+
 /* Lyapunov spectrum from the reset scan: lambda[b, k] = growth[b, k] / (dt T)
  * (paper Section 4.2.1, eq. 20, with the triangular factors accumulated at the resets).  states is
  * optional here (NULL = do not store them).  lambda: [batch, d] doubles. */

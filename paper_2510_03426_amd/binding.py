@@ -25,7 +25,7 @@ EXPORTS = [
     "goom_status_name", "goom_probe_bandwidth", "goom_probe_matrix_unit", "goom_profile_enable", "goom_profile_count", "goom_profile_get", "goom_to_goom", "goom_from_goom", "goom_lmme", "goom_lmme_workspace_bytes",
     "goom_scan", "goom_scan_workspace_bytes", "goom_scan_static", "goom_reduce", "goom_reduce_workspace_bytes",
     "goom_scan_real", "goom_scan_real_workspace_bytes", "goom_reduce_real", "goom_reduce_real_workspace_bytes",
-    "goom_scan_reset", "goom_scan_reset_workspace_bytes", "goom_lyapunov_spectrum",
+    "goom_scan_reset", "goom_scan_reset_workspace_bytes", "goom_scan_reset_tree", "goom_scan_reset_tree_workspace_bytes", "goom_lyapunov_spectrum",
     "goom_lyapunov_spectrum_per_step", "goom_lyapunov_spectrum_per_step_workspace_bytes",
     "goom_largest_lyapunov", "goom_largest_lyapunov_workspace_bytes",
     "goom_affine_scan", "goom_affine_scan_workspace_bytes", "goom_affine_scan_scaled",
@@ -96,6 +96,9 @@ def load_library():
     lib.goom_scan_reset.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, pr, vp, sz]
     lib.goom_scan_reset_workspace_bytes.argtypes = [i64, i32, i64, i32, pr]
     lib.goom_scan_reset_workspace_bytes.restype = sz
+    lib.goom_scan_reset_tree.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, pr, vp, sz]
+    lib.goom_scan_reset_tree_workspace_bytes.argtypes = [i64, i32, i64, i32]
+    lib.goom_scan_reset_tree_workspace_bytes.restype = sz
     lib.goom_lyapunov_spectrum.argtypes = [vp, vp, vp, vp, vp, i64, i32, C.c_double, i64, i32, pr, vp, sz]
     lib.goom_lyapunov_spectrum_per_step.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, C.c_double, i64, i32, pr, vp, sz]
     lib.goom_lyapunov_spectrum_per_step_workspace_bytes.argtypes = [i64, i32, i64, i32, pr, i32, i32]
@@ -385,6 +388,23 @@ class Goom:
         self._check(self.lib.goom_scan_reset(self._ctx, _ptr(jac), _ptr(s0), _ptr(states), _ptr(flags), _ptr(growth),
                                              T, d, batch, code, C.byref(opts), _ptr(ws), wsn))
         return states, flags, growth
+
+    def scan_reset_tree(self, jac, s0=None, policy: int = RESET_COLINEAR, cos_threshold: float = 0.99):
+        """The selective-resetting scan in the order of the paper's parallel prefix scan; returns (states, flags)."""
+        torch = self.torch
+        code = _dtype_code(jac)
+        T, d, _ = jac.shape[-3:]
+        lead = jac.shape[:-3]
+        batch = 1
+        for s in lead:
+            batch *= s
+        opts = ResetOpts(0, policy, cos_threshold)
+        states = torch.empty(lead + (T, d, d), dtype=jac.dtype, device=jac.device)
+        flags = torch.zeros(lead + (T,), dtype=torch.uint8, device=jac.device)
+        ws, wsn = self.workspace(self.lib.goom_scan_reset_tree_workspace_bytes(T, d, batch, code))
+        self._check(self.lib.goom_scan_reset_tree(self._ctx, _ptr(jac), _ptr(s0), _ptr(states), _ptr(flags), T, d, batch, code,
+                                                  C.byref(opts), _ptr(ws), wsn))
+        return states, flags
 
     def lyapunov_spectrum(self, jac, dt: float, s0=None, chunk_len: int = 0, policy: int = RESET_ALWAYS,
                           cos_threshold: float = 0.99):

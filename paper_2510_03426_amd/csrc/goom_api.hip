@@ -1144,6 +1144,27 @@ int goom_scan_reset(goom_ctx *ctx, const void *J, const void *S0, void *states, 
     return run_reset(ctx, J, S0, states, reset_flags, growth, 1.0, T, d, batch, dtype, opts, workspace, workspace_bytes);
 }
 
+size_t goom_scan_reset_tree_workspace_bytes(int64_t T, int d, int64_t batch, int dtype)
+{
+    if (T <= 0 || d <= 0 || batch <= 0 || d > 64 || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
+    return reset_tree_workspace_bytes(T, d, batch, dtype);
+}
+
+int goom_scan_reset_tree(goom_ctx *ctx, const void *J, const void *S0, void *states, uint8_t *reset_flags, int64_t T, int d, int64_t batch,
+                         int dtype, const goom_reset_opts *opts, void *workspace, size_t workspace_bytes)
+{
+    if (int s = check_common(ctx, dtype)) return s;
+    if (!J || !states) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    if (T <= 0 || batch <= 0 || d <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive (T=%lld d=%d batch=%lld)", (long long)T, d, (long long)batch);
+    if (d > 64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 64 (d=%d)", d);
+    const int policy = opts ? opts->policy : GOOM_RESET_COLINEAR;
+    if (policy < GOOM_RESET_NEVER || policy > GOOM_RESET_ALWAYS) return fail(ctx, GOOM_EINVAL, "unknown reset policy %d", policy);
+    if (!aligned(J, 16) || (S0 && !aligned(S0, 16)) || !aligned(states, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
+    if (int s = check_workspace(ctx, workspace, workspace_bytes, reset_tree_workspace_bytes(T, d, batch, dtype))) return s;
+    if (int s = need_ctx(ctx)) return s;
+    return run_reset_tree(ctx, J, S0, states, reset_flags, T, d, batch, dtype, policy, opts ? opts->cos_threshold : 0.99f, workspace);
+}
+
 int goom_lyapunov_spectrum(goom_ctx *ctx, const void *J, const void *S0, void *states, double *lambda, int64_t T, int d,
                            double dt, int64_t batch, int dtype, const goom_reset_opts *opts, void *workspace,
                            size_t workspace_bytes)

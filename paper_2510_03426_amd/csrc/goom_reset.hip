@@ -22,6 +22,8 @@
 // of the logarithms.  The chain of chunks is inherently serial (each reset depends on the
 // previous one), so this phase is latency bound: what counts is the length of the dependent
 // instruction chain per chunk, which is why it runs without a single workgroup barrier.
+#include <cstring>
+
 #include "goom_internal.h"
 
 namespace {
@@ -648,6 +650,174 @@ template <int DP, typename IO> __global__ __launch_bounds__(64) void reset_carry
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// The selective-resetting scan in the order of the paper's own parallel prefix scan (Section 5, eq. 28;
+// Appendix C).  Elements (X_0, A_1, ..., A_T) are GOOM matrices; parallel step k works on blocks of 2^k
+// elements, updating every element of a block's upper half from the last element of its lower half.  With all
+// bias slots zero at the start every tuple (A*, B*) has one non-zero slot, so an element is one matrix M and a
+// flag "has been reset" (the bias slot is the occupied one): a flagged element ignores what precedes it
+// (A* = 0), an unflagged one becomes LMME(M_curr, M_prev) and inherits the flag of prev.  Before each parallel
+// step every unflagged element that S selects is replaced by R(M) and flagged (tree_reset_kernel); the
+// products of a step are batched LMMEs of the chain kernel, scattered back by tree_scatter_kernel.
+struct TreeResetArgs {
+    void *M;             // [n][d][d] GOOMs of one batch item, n = T + 1 elements
+    unsigned char *flag; // [n]
+    long long n;
+    int d;
+    int policy;
+    float cos_threshold;
+};
+
+template <int DP, typename IO> __global__ __launch_bounds__(64) void tree_reset_kernel(TreeResetArgs a)
+{
+    constexpr int KT = DP / 16;
+    __shared__ __align__(32) WaveD<DP> s;
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, c = lane & 15;
+    const int d = a.d;
+    const long long i = blockIdx.x;
+    if (a.flag[i] || a.policy < 0) return; // whole wave
+    IO *mp = static_cast<IO *>(a.M) + (size_t)i * d * d * 2;
+    // columns scaled to a largest entry of 1 (identity block past d)
+    d4 Z[KT][KT];
+    bool any = false;
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) {
+        const int col = 16 * nt + c;
+        double re[KT][4], im[KT][4];
+        double cmax = -__builtin_huge_val();
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * mt + 4 * v + g;
+                double r = row == col ? 0.0 : -__builtin_huge_val(), im_ = 0.0;
+                if (row < d && col < d) {
+                    r = (double)mp[((size_t)row * d + col) * 2];
+                    im_ = (double)mp[((size_t)row * d + col) * 2 + 1];
+                    any = any || r > -__builtin_huge_val();
+                }
+                re[mt][v] = r;
+                im[mt][v] = im_;
+                cmax = fmax(cmax, r);
+            }
+        cmax = fmax(cmax, __shfl_xor(cmax, 16, 64));
+        cmax = fmax(cmax, __shfl_xor(cmax, 32, 64));
+        const bool zero_col = !(cmax > -__builtin_huge_val());
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                double x = zero_col ? 0.0 : exp(re[mt][v] - cmax);
+                if ((int)rint(im[mt][v] * 0.318309886183790671538) & 1) x = -x;
+                Z[nt][mt][v] = x;
+            }
+    }
+    if (__builtin_amdgcn_ballot_w64(any) == 0) return; // a zero matrix is never selected
+    bool sel = a.policy == 1;
+    if (!sel) {
+        // squared cosines between columns, tile by tile of the Gram matrix
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt) {
+            d4 Gd = {0., 0., 0., 0.};
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) Gd = mfma8(Z[nt][kt][v], Z[nt][kt][v], Gd);
+            double dsel = Gd[0];
+            dsel = (c >> 2) == 1 ? Gd[1] : dsel;
+            dsel = (c >> 2) == 2 ? Gd[2] : dsel;
+            dsel = (c >> 2) == 3 ? Gd[3] : dsel;
+            if (g == (c & 3)) s.diag[16 * nt + c] = dsel;
+        }
+        wave_sync();
+        bool hit = false;
+        const double thr2 = (double)a.cos_threshold * (double)a.cos_threshold;
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt) {
+            const double dc = s.diag[16 * nt + c];
+#pragma unroll
+            for (int mt = 0; mt <= nt; ++mt) {
+                d4 Gt = {0., 0., 0., 0.};
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) Gt = mfma8(Z[mt][kt][v], Z[nt][kt][v], Gt);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = 16 * mt + 4 * v + g, col = 16 * nt + c;
+                    const double dr = s.diag[row];
+                    if (row < col && col < d && Gt[v] * Gt[v] > thr2 * dr * dc) hit = true;
+                }
+            }
+        }
+        wave_sync();
+        sel = __builtin_amdgcn_ballot_w64(hit) != 0;
+    }
+    if (!sel) return;
+    double piv[KT], ce[KT];
+    const double amp = qr_panels_d<DP>(Z, piv, ce, s, g, c);
+    if (amp > (sizeof(IO) == 4 ? 1.0e10 : 1.0e3)) (void)qr_panels_d<DP>(Z, piv, ce, s, g, c);
+    const IO pi = sizeof(IO) == 4 ? (IO)3.14159274101257324219f : (IO)3.14159265358979311600;
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * mt + 4 * v + g, col = 16 * nt + c;
+                if (row < d && col < d) {
+                    const double q = Z[nt][mt][v];
+                    mp[((size_t)row * d + col) * 2] = (IO)(q != 0.0 ? log(fabs(q)) : -__builtin_huge_val());
+                    mp[((size_t)row * d + col) * 2 + 1] = q < 0.0 ? pi : (IO)0;
+                }
+            }
+    if (lane == 0) a.flag[i] = 1;
+}
+
+// After the products of a parallel step: element i = block * 2 half + half + u takes tmp[block][u] unless it is
+// flagged, and inherits the flag of j = block * 2 half + half - 1.  One workgroup per element.
+template <typename IO> __global__ __launch_bounds__(256) void tree_scatter_kernel(IO *M, const IO *tmp, unsigned char *flag, long long n, int d,
+                                                                                  long long half)
+{
+    const long long e = blockIdx.x; // index among the updated elements, block by block
+    const long long block = e / half, u = e % half;
+    const long long i = block * 2 * half + half + u, j = block * 2 * half + half - 1;
+    if (i >= n) return;
+    const unsigned char fi = flag[i], fj = flag[j];
+    __syncthreads();
+    if (!fi) {
+        const size_t nn = (size_t)d * d * 2;
+        for (size_t q = threadIdx.x; q < nn; q += 256) M[(size_t)i * nn + q] = tmp[(size_t)e * nn + q];
+        if (threadIdx.x == 0) flag[i] = fj;
+    }
+}
+
+// elements of one batch item: X_0 (given, or the identity) and the T matrices; flags cleared
+template <typename IO> __global__ __launch_bounds__(256) void tree_init_kernel(const IO *J, const IO *S0, IO *M, unsigned char *flag, long long n, int d)
+{
+    const long long i = blockIdx.x;
+    const size_t nn = (size_t)d * d * 2;
+    const IO ninf = sizeof(IO) == 4 ? (IO)-__builtin_huge_valf() : (IO)-__builtin_huge_val();
+    for (size_t q = threadIdx.x; q < nn; q += 256) {
+        IO v;
+        if (i > 0) v = J[(size_t)(i - 1) * nn + q];
+        else if (S0) v = S0[q];
+        else v = (q & 1) ? (IO)0 : (((q / 2) / d == (q / 2) % d) ? (IO)0 : ninf);
+        M[(size_t)i * nn + q] = v;
+    }
+    if (threadIdx.x == 0) flag[i] = 0;
+}
+
+template <typename IO> __global__ __launch_bounds__(256) void tree_finish_kernel(const IO *M, const unsigned char *flag, IO *states, unsigned char *out_flags,
+                                                                                 long long n, int d)
+{
+    const long long t = blockIdx.x; // state after step t + 1 = element t + 1
+    const size_t nn = (size_t)d * d * 2;
+    for (size_t q = threadIdx.x; q < nn; q += 256) states[(size_t)t * nn + q] = M[(size_t)(t + 1) * nn + q];
+    if (out_flags && threadIdx.x == 0) out_flags[t] = flag[t + 1];
+}
+
 // Spectrum from the input states (paper Section 4.2.1, groups (b)-(d)): one wave per step t.
 // The input state S_{t-1} is log-scaled column by column and exponentiated, its QR gives the
 // orthonormal basis Q_{t-1}; J_t (scaled by one power of two for the whole matrix) is applied to
@@ -967,6 +1137,85 @@ int launch_uniform_u0(goom_ctx *ctx, void *u, long long batch, int d, int dtype)
     else
         hipLaunchKernelGGL(uniform_u0_kernel<double>, dim3(blocks), dim3(256), 0, ctx->stream, static_cast<double *>(u), n, d);
     return check_hip(ctx, hipGetLastError(), "launch uniform_u0_kernel");
+}
+
+size_t reset_tree_workspace_bytes(long long T, int d, long long batch, int dtype)
+{
+    const size_t mat = (size_t)d * d * 2 * (dtype == GOOM_C64 ? 4 : 8);
+    return align_up((size_t)batch * (T + 1) * mat, 256) + align_up((size_t)(T + 1) * mat, 256) + align_up((size_t)batch * (T + 1), 256);
+}
+
+template <typename IO> static int run_reset_tree_t(goom_ctx *ctx, const void *J, const void *S0, void *states, unsigned char *out_flags, long long T, int d,
+                                                   long long batch, int dtype, int policy, float cos_threshold, void *ws)
+{
+    const long long n = T + 1;
+    const size_t mat = (size_t)d * d * 2 * sizeof(IO);
+    unsigned char *w = static_cast<unsigned char *>(ws);
+    unsigned char *Mall = w;
+    unsigned char *tmp = w + align_up((size_t)batch * n * mat, 256);
+    unsigned char *flags = tmp + align_up((size_t)n * mat, 256);
+    const int dp = padded_dim(d);
+    if (n > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
+    for (long long b = 0; b < batch; ++b) {
+        IO *M = reinterpret_cast<IO *>(Mall + (size_t)b * n * mat);
+        unsigned char *flag = flags + (size_t)b * n;
+        hipLaunchKernelGGL(tree_init_kernel<IO>, dim3((unsigned)n), dim3(256), 0, ctx->stream, static_cast<const IO *>(J) + (size_t)b * T * d * d * 2,
+                           S0 ? static_cast<const IO *>(S0) + (size_t)b * d * d * 2 : nullptr, M, flag, n, d);
+        for (long long half = 1; half < n; half *= 2) {
+            TreeResetArgs a;
+            a.M = M;
+            a.flag = flag;
+            a.n = n;
+            a.d = d;
+            a.policy = policy;
+            a.cos_threshold = cos_threshold;
+            prof_begin(ctx, "reset_tree_select_and_reset");
+            if (dp == 16) hipLaunchKernelGGL((tree_reset_kernel<16, IO>), dim3((unsigned)n), dim3(64), 0, ctx->stream, a);
+            else if (dp == 32) hipLaunchKernelGGL((tree_reset_kernel<32, IO>), dim3((unsigned)n), dim3(64), 0, ctx->stream, a);
+            else hipLaunchKernelGGL((tree_reset_kernel<64, IO>), dim3((unsigned)n), dim3(64), 0, ctx->stream, a);
+            prof_end(ctx);
+            if (int st = check_hip(ctx, hipGetLastError(), "launch tree_reset_kernel")) return st;
+            // products of this parallel step: whole blocks, then the ragged last one
+            const long long full = n / (2 * half), rest = n % (2 * half) > half ? n % (2 * half) - half : 0;
+            for (int part = 0; part < 2; ++part) {
+                const long long items = part == 0 ? full : (rest ? 1 : 0), steps = part == 0 ? half : rest;
+                if (items == 0) continue;
+                const long long first = part == 0 ? 0 : full * 2 * half; // first element of the first block of this part
+                ChainLaunch l;
+                std::memset(&l, 0, sizeof l);
+                l.dtype = dtype;
+                l.n = l.d = l.m = d;
+                l.left = reinterpret_cast<unsigned char *>(M) + (size_t)(first + half) * mat;
+                l.left_batch_stride = (long long)(2 * half * mat);
+                l.left_step_stride = (long long)mat;
+                l.steps = steps;
+                l.chunk_len = 1;
+                l.chunks_launched = steps;
+                l.batch = items;
+                l.init_mode = 2;
+                l.init = reinterpret_cast<unsigned char *>(M) + (size_t)(first + half - 1) * mat;
+                l.init_stride = (long long)(2 * half * mat);
+                l.out_goom = tmp + (size_t)(part == 0 ? 0 : full * half) * mat;
+                l.label = "reset_tree_products";
+                if (int st = launch_chain(ctx, l)) return st;
+            }
+            const long long updated = full * half + rest;
+            if (updated > 0)
+                hipLaunchKernelGGL(tree_scatter_kernel<IO>, dim3((unsigned)updated), dim3(256), 0, ctx->stream, M, reinterpret_cast<const IO *>(tmp), flag, n, d, half);
+            if (int st = check_hip(ctx, hipGetLastError(), "launch tree_scatter_kernel")) return st;
+        }
+        hipLaunchKernelGGL(tree_finish_kernel<IO>, dim3((unsigned)T), dim3(256), 0, ctx->stream, M, flag, static_cast<IO *>(states) + (size_t)b * T * d * d * 2,
+                           out_flags ? out_flags + (size_t)b * T : nullptr, n, d);
+        if (int st = check_hip(ctx, hipGetLastError(), "launch tree_finish_kernel")) return st;
+    }
+    return GOOM_OK;
+}
+
+int run_reset_tree(goom_ctx *ctx, const void *J, const void *S0, void *states, unsigned char *out_flags, long long T, int d, long long batch,
+                   int dtype, int policy, float cos_threshold, void *ws)
+{
+    return dtype == GOOM_C64 ? run_reset_tree_t<float>(ctx, J, S0, states, out_flags, T, d, batch, dtype, policy, cos_threshold, ws)
+                             : run_reset_tree_t<double>(ctx, J, S0, states, out_flags, T, d, batch, dtype, policy, cos_threshold, ws);
 }
 
 int launch_reset_carry(goom_ctx *ctx, const ResetLaunch &l)

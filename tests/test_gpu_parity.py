@@ -511,6 +511,56 @@ def test_reset_scan_always_matches_sequential_oracle(G, oracle, T, d, L, ctype):
     assert np.abs(lam_gpu - lam_ref).max() < 1e-9 and np.abs(lam_gpu - lam_qr).max() < 1e-4
 
 
+@pytest.mark.parametrize("T,d,batch,ctype,policy,thr", [(11, 4, 2, np.complex128, 0, 0.9), (37, 8, 1, np.complex128, 0, 0.97), (64, 16, 1, np.complex128, 0, 0.9),
+                                                        (23, 6, 2, np.complex64, 0, 0.9), (40, 32, 1, np.complex64, 0, 0.8), (9, 4, 1, np.complex64, -1, 0.9),
+                                                        (9, 4, 1, np.complex128, 1, 0.9), (33, 64, 1, np.complex128, 0, 0.7)])
+def test_reset_scan_in_the_papers_tree_order(G, oracle, T, d, batch, ctype, policy, thr):
+    """The selective-resetting transformation applied in the order of the paper's own parallel scan (Section 5, eq. 28;
+    Appendix C) against the oracle's literal (A*, B*) tuples over reals in the same order.  Which compounds are reset is
+    decided by cosines; the inputs are drawn so that no decision sits near its threshold (checked on the oracle side)."""
+    comp = np.float32 if ctype == np.complex64 else np.float64
+    rng = np.random.default_rng(100 + T + d)
+    A = (rng.standard_normal((batch, T, d, d)) / math.sqrt(d) * 1.5).astype(comp)
+    X0 = rng.standard_normal((batch, d, d)).astype(comp)
+    say(f"tree-order reset scan T={T} d={d} batch={batch} {np.dtype(ctype).name} policy={policy} threshold={thr}")
+    states, flags = G.scan_reset_tree(dev(oracle.to_goom(A)), dev(oracle.to_goom(X0)), policy=policy, cos_threshold=thr)
+    got, gflags = host(states), host(flags)
+    nreset = 0
+    for b in range(batch):
+        want, was = oracle.reset_scan_tree_real(X0[b].astype(np.float64), A[b].astype(np.float64), policy=policy, cos_threshold=thr)
+        # decisions are robust: the same flags come out with the threshold moved a little either way
+        for dthr in (-1e-3, 1e-3):
+            if policy == 0:
+                assert np.array_equal(oracle.reset_scan_tree_real(X0[b].astype(np.float64), A[b].astype(np.float64), policy=policy, cos_threshold=thr + dthr)[1], was)
+        assert np.array_equal(gflags[b].astype(bool), was[1:])
+        nreset += int(was[1:].sum())
+        val = np.where(got[b].imag != 0, -1.0, 1.0) * np.exp(got[b].real.astype(np.float64))
+        err = np.linalg.norm(val - want[1:], axis=1) / np.linalg.norm(want[1:], axis=1)
+        # The float path forms every compound with float products, and an orthonormal factor's later columns hang on
+        # the small differences between nearly parallel columns: columns that move by more than 1/16 of the bound
+        # when the oracle's inputs are perturbed by 64 units in the last place of the component type (a compound of
+        # 2^k elements has been through k float products of d terms each, about k sqrt(d) units relative to a column's
+        # norm) are left out
+        bound = 2e-4 if comp == np.float32 else 1e-9
+        eta = 2.0 ** -18 if comp == np.float32 else 2.0 ** -47
+        sens = np.zeros((T, d))
+        for _ in range(4):  # (the last column of a factor can flip its sign outright: several probes, so that one of them shows it)
+            pert, pwas = oracle.reset_scan_tree_real(X0[b].astype(np.float64) * (1 + eta * rng.standard_normal((d, d))),
+                                                     A[b].astype(np.float64) * (1 + eta * rng.standard_normal((T, d, d))), policy=policy, cos_threshold=thr)
+            assert np.array_equal(pwas, was)
+            sens = np.maximum(sens, np.linalg.norm(pert[1:] - want[1:], axis=1) / np.linalg.norm(want[1:], axis=1))
+        well = sens <= bound / 16
+        say(f"  item {b}: {int(was[1:].sum())} of {T} states descend from a reset; column-wise relative error max {err[well].max():.2e} "
+            f"over the {well.mean():.1%} of the columns that are determined at this precision")
+        assert err[well].max() < bound and well.mean() > (0.1 if comp == np.float32 else 0.9)
+    if policy == 0:
+        assert nreset > 0
+    # S == 0: the plain scan
+    if policy == -1:
+        plain = host(G.scan(dev(oracle.to_goom(A)), init=dev(oracle.to_goom(X0))))
+        assert np.allclose(plain.real, got.real, rtol=1e-4, atol=1e-3) and np.array_equal(plain.imag != 0, got.imag != 0)
+
+
 def test_reset_scan_colinear_policy_and_initial_state(G, oracle):
     from paper_2510_03426_amd import RESET_COLINEAR
     T, d, L = 400, 8, 10
