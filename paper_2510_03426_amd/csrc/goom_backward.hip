@@ -131,28 +131,47 @@ template <typename R> __global__ __launch_bounds__(256) void bwd_prepare_kernel(
     }
 }
 
-// Gradients from the scaled adjoints mu[b, s] = lam[b, T - 1 - s] e^(c_{T-1-s}) (GOOMs), one workgroup per (b, t):
+// Gradients from the scaled adjoints mu[b, s] = lam[b, T - 1 - s] e^(c_{T-1-s}) (GOOMs), one wave per (b, t), no
+// workgroup barrier:
 //   gA[b, t, i, j] = lam_t[i] A_t[i, j] h_{t-1}[j],   gb[b, t, i] = lam_t[i] b_t[i].
-// Sums of three log-magnitudes are formed in double (the adjoint and the state are large and opposite).
-template <typename R> __global__ __launch_bounds__(256) void bwd_grad_kernel(const typename C2<R>::type *__restrict__ A,
-                                                                             const typename C2<R>::type *__restrict__ bias,
-                                                                             const typename C2<R>::type *__restrict__ h0,
-                                                                             const typename C2<R>::type *__restrict__ H,
-                                                                             const typename C2<R>::type *__restrict__ mu, R *__restrict__ gA,
-                                                                             R *__restrict__ gb, long long T, int d)
+// Sums of three log-magnitudes are formed in double (the adjoint and the state are large and opposite); the wave
+// keeps the adjoint's and the previous state's log-magnitudes and signs in LDS words of its own.
+constexpr int kGradWaves = 4;
+
+template <typename R> __global__ __launch_bounds__(kGradWaves * 64) void bwd_grad_kernel(const typename C2<R>::type *__restrict__ A,
+                                                                                         const typename C2<R>::type *__restrict__ bias,
+                                                                                         const typename C2<R>::type *__restrict__ h0,
+                                                                                         const typename C2<R>::type *__restrict__ H,
+                                                                                         const typename C2<R>::type *__restrict__ mu, R *__restrict__ gA,
+                                                                                         R *__restrict__ gb, long long T, int d, long long nsteps)
 {
     typedef typename C2<R>::type c2;
     extern __shared__ __align__(16) unsigned char smem[];
-    double *lre = reinterpret_cast<double *>(smem); // [d] adjoint log-magnitudes
-    double *pre = lre + d;                          // [d] log-magnitudes of the previous state
-    int *lneg = reinterpret_cast<int *>(pre + d);   // [d]
-    int *pneg = lneg + d;                           // [d]
-    __shared__ R red[256];
-    const long long b = blockIdx.x / T, t = blockIdx.x % T;
-    const int tid = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const long long step = (long long)blockIdx.x * kGradWaves + wave;
+    if (step >= nsteps) return; // whole wave
+    const long long b = step / T, t = step % T;
+    // this wave's words: lre[d], pre[d] (double), signs packed with them as separate int arrays
+    double *lre = reinterpret_cast<double *>(smem) + (size_t)wave * 2 * d;
+    double *pre = lre + d;
+    int *lneg = reinterpret_cast<int *>(reinterpret_cast<double *>(smem) + (size_t)kGradWaves * 2 * d) + (size_t)wave * 2 * d;
+    int *pneg = lneg + d;
     const double ninf = -__builtin_huge_val();
-    const double ct = (double)state_scale<R>(H + (size_t)(b * T + t) * d, d, red);
-    for (int i = tid; i < d; i += 256) {
+    // c_t: the whole number nearest the largest log-magnitude of h_t
+    const c2 *ht = H + (size_t)(b * T + t) * d;
+    R top = sizeof(R) == 4 ? (R)-__builtin_huge_valf() : (R)-__builtin_huge_val();
+    for (int i = lane; i < d; i += 64) {
+        const R v = ht[i].x;
+        top = v > top ? v : top;
+    }
+    for (int sft = 32; sft > 0; sft >>= 1) {
+        const R o = __shfl_xor(top, sft, 64);
+        top = o > top ? o : top;
+    }
+    const bool finite = (double)top > ninf && (double)top < -ninf;
+    const double ct = finite ? __builtin_rint((double)top) : 0.0;
+    for (int i = lane; i < d; i += 64) {
         const c2 l = mu[(size_t)(b * T + (T - 1 - t)) * d + i];
         lre[i] = (double)l.x - ct; // -inf stays -inf
         lneg[i] = odd_phase<R>(l.y) ? 1 : 0;
@@ -162,20 +181,36 @@ template <typename R> __global__ __launch_bounds__(256) void bwd_grad_kernel(con
         pre[i] = (double)p.x;
         pneg[i] = odd_phase<R>(p.y) ? 1 : 0;
     }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const c2 *ap = A + (size_t)(b * T + t) * d * d;
     R *op = gA + (size_t)(b * T + t) * d * d;
-    for (int e = tid; e < d * d; e += 256) {
-        const int i = e / d, j = e % d;
-        const c2 a = ap[e];
+    auto one = [&](int e, c2 a) {
+        const int i = e / d, j = e - i * d;
         const double s = lre[i] + (double)a.x + pre[j];
         const bool live = lre[i] > ninf && (double)a.x > ninf && pre[j] > ninf;
         const double v = live ? exp_for<R>(s) : 0.0;
         const bool neg = (lneg[i] ^ pneg[j] ^ (odd_phase<R>(a.y) ? 1 : 0)) != 0;
-        op[e] = (R)(neg ? -v : v);
+        return (R)(neg ? -v : v);
+    };
+    const int nn = d * d;
+    if (sizeof(R) == 4 && (nn & 1) == 0) {
+        // two adjacent entries per lane and pass: one 16-byte load, one 8-byte store
+        const float4 *ap4 = reinterpret_cast<const float4 *>(ap);
+        float2 *op2 = reinterpret_cast<float2 *>(op);
+        for (int q = lane; q < nn / 2; q += 64) {
+            const float4 w = ap4[q];
+            float2 o;
+            o.x = (float)one(2 * q, c2{(R)w.x, (R)w.y});
+            o.y = (float)one(2 * q + 1, c2{(R)w.z, (R)w.w});
+            op2[q] = o;
+        }
+    } else {
+        for (int e = lane; e < nn; e += 64) op[e] = one(e, ap[e]);
     }
     if (gb) {
-        for (int i = tid; i < d; i += 256) {
+        for (int i = lane; i < d; i += 64) {
             const c2 bb = bias[(size_t)(b * T + t) * d + i];
             const bool live = lre[i] > ninf && (double)bb.x > ninf;
             const double v = live ? exp_for<R>(lre[i] + (double)bb.x) : 0.0;
@@ -260,11 +295,12 @@ template <typename R> static int bwd_grad_t(goom_ctx *ctx, const void *A, const 
                                             void *gb, void *gh0, long long T, int d, long long batch)
 {
     typedef typename C2<R>::type c2;
-    const size_t lds = (size_t)d * (2 * sizeof(double) + 2 * sizeof(int));
+    const size_t lds = (size_t)kGradWaves * d * (2 * sizeof(double) + 2 * sizeof(int));
+    const long long nsteps = batch * T;
     prof_begin(ctx, "affine_backward_gradients");
-    hipLaunchKernelGGL(bwd_grad_kernel<R>, dim3((unsigned)(batch * T)), dim3(256), lds, ctx->stream, static_cast<const c2 *>(A),
-                       static_cast<const c2 *>(bias), static_cast<const c2 *>(h0), static_cast<const c2 *>(H), static_cast<const c2 *>(mu),
-                       static_cast<R *>(gA), static_cast<R *>(gb), T, d);
+    hipLaunchKernelGGL(bwd_grad_kernel<R>, dim3((unsigned)((nsteps + kGradWaves - 1) / kGradWaves)), dim3(kGradWaves * 64), lds, ctx->stream,
+                       static_cast<const c2 *>(A), static_cast<const c2 *>(bias), static_cast<const c2 *>(h0), static_cast<const c2 *>(H),
+                       static_cast<const c2 *>(mu), static_cast<R *>(gA), static_cast<R *>(gb), T, d, nsteps);
     if (gh0) hipLaunchKernelGGL(bwd_h0_kernel<R>, dim3((unsigned)batch), dim3(128), 0, ctx->stream, static_cast<const R *>(gA), static_cast<R *>(gh0), T, d);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch bwd_grad_kernel");

@@ -230,7 +230,7 @@ def test_config3_batched_lmme_full_size(G, oracle, ctype):
     for p in pairs:
         ah, bh = host(a[p]), host(b[p])
         re, sg, kap, well = with_sensitivity(lambda x, y: oracle.lmme(x, y, return_kappa=True), [ah, bh], comp, nprobe=1)
-        compare(host(c[p]), re, sg, kap, name=f"config 3 {ctype} pair {p}", max_ill_fraction=0.01, well=well)
+        compare(host(c[p]), re, sg, kap, name=f"config 3 {ctype} pair {p}", max_ill_fraction=0.002, well=well)
     del a, b, c
 
 

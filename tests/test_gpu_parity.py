@@ -233,7 +233,7 @@ def test_lmme_wide_range_needs_exact_repair(G, oracle, ctype):
     if ctype == np.complex64:
         assert lost.mean() > 0.5
     got = host(G.lmme(dev(A), dev(B), flags=LMME_EXACT))
-    compare(got, re, sg, kap, name=f"lmme exact {np.dtype(ctype).name}", max_ill_fraction=0.02)
+    compare(got, re, sg, kap, name=f"lmme exact {np.dtype(ctype).name}", max_ill_fraction=0.002)
     # the same call through the C ABI without the optional workspace (the repair pass then takes the row and column
     # maxima itself instead of receiving the product's shifts)
     import torch
@@ -241,7 +241,7 @@ def test_lmme_wide_range_needs_exact_repair(G, oracle, ctype):
     a_d, b_d = dev(A), dev(B)
     out = torch.empty((b, n, m), dtype=a_d.dtype, device=a_d.device)
     G._check(G.lib.goom_lmme(G._ctx, bnd._ptr(a_d), bnd._ptr(b_d), bnd._ptr(out), b, n, d, m, bnd._dtype_code(a_d), LMME_EXACT, None, 0))
-    compare(host(out), re, sg, kap, name=f"lmme exact {np.dtype(ctype).name}, no workspace", max_ill_fraction=0.02)
+    compare(host(out), re, sg, kap, name=f"lmme exact {np.dtype(ctype).name}, no workspace", max_ill_fraction=0.002)
     # benign data: everything certifies, the repair pass changes nothing
     A2 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 27, 7, 2 * 64 * 64).reshape(2, 64, 64))
     B2 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 28, 8, 2 * 64 * 64).reshape(2, 64, 64))
@@ -260,7 +260,7 @@ def test_lmme_partly_repaired_blocks(G, oracle, sigma):
     fast, got = host(G.lmme(dev(A), dev(B), flags=LMME_FAST)), host(G.lmme(dev(A), dev(B), flags=LMME_EXACT))
     changed = (fast.view(np.uint32) != got.view(np.uint32)).reshape(b, n, m, 2).any(axis=-1)
     say(f"lmme sigma {sigma}: the repair pass rewrote {changed.mean():.1%} of the outputs")
-    compare(got, re, sg, kap, name=f"lmme sigma {sigma}", max_ill_fraction=0.02)
+    compare(got, re, sg, kap, name=f"lmme sigma {sigma}", max_ill_fraction=0.002)
 
 
 # -------------------------------------------------------------------------------- scan
@@ -464,7 +464,7 @@ def test_reset_scan_never_equals_plain_scan(G, oracle, T, d, L):
     states, flags, growth = G.scan_reset(dev(Jz), chunk_len=L, policy=RESET_NEVER)
     fn = lambda mats: oracle.scan(mats, init=oracle.to_goom(np.eye(d, dtype=np.float32)), return_kappa=True)
     re, sg, kap, well = with_sensitivity(fn, [Jz], np.float32, nprobe=3)
-    compare(host(states), re, sg, kap, name=f"reset never T{T}d{d}", max_ill_fraction=0.05, well=well)
+    compare(host(states), re, sg, kap, name=f"reset never T{T}d{d}", max_ill_fraction=0.02, well=well)
     assert host(flags).sum() == 0
 
 
@@ -895,13 +895,13 @@ def test_lmme_large_shapes_complex128(G, oracle, shape):
     say(f"large lmme complex128 {shape}")
     re, sg, kap = oracle.lmme(A, B, return_kappa=True)
     got = host(G.lmme(dev(A), dev(B)))
-    compare(got, re, sg, kap, name=f"large lmme c128 {shape}", max_ill_fraction=0.01)
+    compare(got, re, sg, kap, name=f"large lmme c128 {shape}", max_ill_fraction=0.002)
     if n * d * m <= 256 ** 3:
         # log-magnitudes N(0, 200^2): the scaled product with its repair pass
         A2, B2 = si.wide_range_goom_pairs(si.BASE_SEED + 66, b, n, d, m, sigma=200.0, dtype=np.complex128)
         re, sg, kap = oracle.lmme(A2, B2, return_kappa=True)
         got = host(G.lmme(dev(A2), dev(B2), flags=LMME_EXACT))
-        compare(got, re, sg, kap, name=f"large lmme c128 wide, repaired {shape}", max_ill_fraction=0.01)
+        compare(got, re, sg, kap, name=f"large lmme c128 wide, repaired {shape}", max_ill_fraction=0.002)
 
 
 @pytest.mark.parametrize("shape", [(2, 256, 256, 256), (1, 300, 200, 150), (3, 129, 64, 64), (1, 40, 500, 33), (1, 512, 512, 512),
@@ -933,11 +933,11 @@ def test_lmme_large_shapes(G, oracle, shape):
         # with the repair pass every output is claimed, also at a spread that leaves nothing certified
         from paper_2510_03426_amd import LMME_EXACT
         got = host(G.lmme(dev(A2), dev(B2), flags=LMME_EXACT))
-        compare(got, re, sg, kap, name=f"large lmme wide, repaired {shape}", max_ill_fraction=0.05)
+        compare(got, re, sg, kap, name=f"large lmme wide, repaired {shape}", max_ill_fraction=0.002)
         A3, B3 = si.wide_range_goom_pairs(si.BASE_SEED + 69, b, n, d, m, sigma=200.0, dtype=np.complex64)
         re3, sg3, kap3 = oracle.lmme(A3, B3, return_kappa=True)
         got3 = host(G.lmme(dev(A3), dev(B3), flags=LMME_EXACT))
-        compare(got3, re3, sg3, kap3, name=f"large lmme sigma 200, repaired {shape}", max_ill_fraction=0.05)
+        compare(got3, re3, sg3, kap3, name=f"large lmme sigma 200, repaired {shape}", max_ill_fraction=0.002)
 
 
 @pytest.mark.parametrize("T,d,chunk,m,batch", [(24, 256, 0, None, 1), (10, 200, 3, None, 2), (9, 160, 4, 70, 1), (6, 512, 2, None, 1),
@@ -1076,7 +1076,7 @@ def test_degenerate_chains(G, oracle, d):
     out = host(G.scan(dev(Z), chunk_len=4))
     assert np.all(np.isneginf(out[7:].real)) and np.all(out[7:].imag == 0)
     re, sg, kap = oracle.scan(Z[:7], return_kappa=True)
-    compare(out[:7], re, sg, kap, name=f"before the zero factor d{d}", max_ill_fraction=0.3 if d < 4 else 0.06)
+    compare(out[:7], re, sg, kap, name=f"before the zero factor d{d}", max_ill_fraction=0.05 if d < 4 else 0.06)
     assert np.all(np.isneginf(host(G.reduce(dev(Z), chunk_len=4)).real))
     # c) zero rows and zero columns inside factors (all-zero rows of a tile must not produce NaN)
     xr = x.copy()
@@ -1088,7 +1088,7 @@ def test_degenerate_chains(G, oracle, d):
     re, sg, kap = oracle.scan(Z, return_kappa=True)
     assert not np.any(np.isnan(out.real))
     assert np.array_equal(np.isneginf(out.real), np.isneginf(re))
-    compare(out, re, sg, kap, name=f"zero rows and columns d{d}", max_ill_fraction=0.3 if d < 4 else 0.08)
+    compare(out, re, sg, kap, name=f"zero rows and columns d{d}", max_ill_fraction=0.05 if d < 4 else 0.08)
     # d) a single step is the matrix itself, bit for bit where it is finite
     Z1 = oracle.to_goom(x[:1])
     one = host(G.scan(dev(Z1)))
