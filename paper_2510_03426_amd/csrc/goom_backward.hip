@@ -70,57 +70,86 @@ template <typename R> __global__ __launch_bounds__(256) void from_goom_backward_
 //   At[b, s] = A[b, T - s]^T for s >= 1 (the matrix for s = 0 multiplies the zero initial adjoint: written as zeros),
 //   gt[b, s, i] = GOOM(G[b, T - 1 - s, i]) - H[b, T - 1 - s, i]   (zero where G is zero or the state is zero).
 // One workgroup per (b, s); the matrix passes through LDS so that both its read and its write are contiguous.
-// c_t: the whole number nearest the largest log-magnitude of h_t (0 for a zero state); every thread of the workgroup
-// returns the same value (red: d-independent scratch of 256 entries)
-template <typename R> __device__ inline R state_scale(const typename C2<R>::type *h, int d, R *red)
+// c_t: the whole number nearest the largest log-magnitude of h_t (0 for a zero state), the same in every lane of the wave
+template <typename R> __device__ inline R state_scale(const typename C2<R>::type *h, int d)
 {
     const R ninf = sizeof(R) == 4 ? (R)-__builtin_huge_valf() : (R)-__builtin_huge_val();
-    R m = ninf;
-    for (int i = threadIdx.x; i < d; i += 256) {
+    R top = ninf;
+    for (int i = threadIdx.x & 63; i < d; i += 64) {
         const R v = h[i].x;
-        m = v > m ? v : m;
+        top = v > top ? v : top;
     }
-    red[threadIdx.x] = m;
-    __syncthreads();
-    for (int sft = 128; sft > 0; sft >>= 1) {
-        if ((int)threadIdx.x < sft) red[threadIdx.x] = red[threadIdx.x + sft] > red[threadIdx.x] ? red[threadIdx.x + sft] : red[threadIdx.x];
-        __syncthreads();
+    for (int sft = 32; sft > 0; sft >>= 1) {
+        const R o = __shfl_xor(top, sft, 64);
+        top = o > top ? o : top;
     }
-    const R top = red[0];
-    __syncthreads();
     const bool finite = top > ninf && top < -ninf;
     return finite ? (R)__builtin_rint((double)top) : (R)0;
 }
 
-template <typename R> __global__ __launch_bounds__(256) void bwd_prepare_kernel(const typename C2<R>::type *__restrict__ A,
-                                                                                const typename C2<R>::type *__restrict__ H, const R *__restrict__ G,
-                                                                                typename C2<R>::type *__restrict__ At, typename C2<R>::type *__restrict__ gt,
-                                                                                long long T, int d)
+// One wave per (b, s), no workgroup barrier: the matrix passes through LDS words of the wave's own so that both its
+// read and its write are contiguous.
+template <typename R, int NW> __global__ __launch_bounds__(NW * 64) void bwd_prepare_kernel(const typename C2<R>::type *__restrict__ A,
+                                                                                            const typename C2<R>::type *__restrict__ H,
+                                                                                            const R *__restrict__ G, typename C2<R>::type *__restrict__ At,
+                                                                                            typename C2<R>::type *__restrict__ gt, long long T, int d,
+                                                                                            long long nsteps, int direct)
 {
     typedef typename C2<R>::type c2;
     extern __shared__ __align__(16) unsigned char smem[];
-    c2 *tile = reinterpret_cast<c2 *>(smem); // [d][d + 1]
-    __shared__ R red[256];
-    const long long b = blockIdx.x / T, s = blockIdx.x % T;
-    const int tid = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const long long step = (long long)blockIdx.x * NW + wave;
+    if (step >= nsteps) return; // whole wave
+    c2 *tile = reinterpret_cast<c2 *>(smem) + (size_t)wave * d * (d + 1); // [d][d + 1]
+    const long long b = step / T, s = step % T;
     const R ninf = sizeof(R) == 4 ? (R)-__builtin_huge_valf() : (R)-__builtin_huge_val();
     const long long t = T - 1 - s;
-    const R ct = state_scale<R>(H + (size_t)(b * T + t) * d, d, red);
+    const R ct = state_scale<R>(H + (size_t)(b * T + t) * d, d);
     c2 *dst = At + (size_t)(b * T + s) * d * d;
+    const int nn = d * d;
     if (s == 0) {
-        for (int e = tid; e < d * d; e += 256) dst[e] = c2{ninf, (R)0};
+        for (int e = lane; e < nn; e += 64) dst[e] = c2{ninf, (R)0};
     } else {
-        const R delta = ct - state_scale<R>(H + (size_t)(b * T + t + 1) * d, d, red); // c_t - c_{t+1}, a whole number
+        const R delta = ct - state_scale<R>(H + (size_t)(b * T + t + 1) * d, d); // c_t - c_{t+1}, a whole number
         const c2 *src = A + (size_t)(b * T + (T - s)) * d * d;
-        for (int e = tid; e < d * d; e += 256) tile[(e / d) * (d + 1) + e % d] = src[e];
-        __syncthreads();
-        for (int e = tid; e < d * d; e += 256) {
-            c2 v = tile[(e % d) * (d + 1) + e / d];
-            v.x += delta; // -inf stays -inf
-            dst[e] = v;
+        if (direct) { // a matrix too large for LDS (complex128 above 96 x 96): strided reads
+            for (int e = lane; e < nn; e += 64) {
+                c2 v = src[(e % d) * d + e / d];
+                v.x += delta;
+                dst[e] = v;
+            }
+        } else if (sizeof(R) == 4 && (d & 1) == 0) {
+            const float4 *src4 = reinterpret_cast<const float4 *>(src);
+            for (int q = lane; q < nn / 2; q += 64) {
+                const float4 w = src4[q];
+                const int i = (2 * q) / d, j = (2 * q) - i * d;
+                tile[i * (d + 1) + j] = c2{(R)w.x, (R)w.y};
+                tile[i * (d + 1) + j + 1] = c2{(R)w.z, (R)w.w};
+            }
+        } else {
+            for (int e = lane; e < nn; e += 64) tile[(e / d) * (d + 1) + e % d] = src[e];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (direct) {
+        } else if (sizeof(R) == 4 && (d & 1) == 0) {
+            float4 *dst4 = reinterpret_cast<float4 *>(dst);
+            for (int q = lane; q < nn / 2; q += 64) {
+                const int i = (2 * q) / d, j = (2 * q) - i * d; // entries (i, j) and (i, j + 1) of the transpose
+                const c2 u = tile[j * (d + 1) + i], v = tile[(j + 1) * (d + 1) + i];
+                dst4[q] = float4{(float)u.x + (float)delta, (float)u.y, (float)v.x + (float)delta, (float)v.y}; // -inf stays -inf
+            }
+        } else {
+            for (int e = lane; e < nn; e += 64) {
+                c2 v = tile[(e % d) * (d + 1) + e / d];
+                v.x += delta;
+                dst[e] = v;
+            }
         }
     }
-    for (int i = tid; i < d; i += 256) {
+    for (int i = lane; i < d; i += 64) {
         const R gv = G[(size_t)(b * T + t) * d + i];
         const c2 h = H[(size_t)(b * T + t) * d + i];
         c2 o;
@@ -269,19 +298,32 @@ int launch_from_goom_backward(goom_ctx *ctx, const void *y, const void *gx, void
     return check_hip(ctx, hipGetLastError(), "launch from_goom_backward");
 }
 
-template <typename R> static int bwd_prepare_t(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d, long long batch)
+template <typename R, int NW> static int bwd_prepare_launch(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d,
+                                                           long long batch)
 {
     typedef typename C2<R>::type c2;
-    const size_t lds = (size_t)d * (d + 1) * sizeof(c2);
-    auto kern = bwd_prepare_kernel<R>;
+    const size_t tile_bytes = (size_t)d * (d + 1) * sizeof(c2);
+    const int direct = tile_bytes > 150 * 1024 ? 1 : 0;
+    const size_t lds = direct ? 0 : (size_t)NW * tile_bytes;
+    auto kern = bwd_prepare_kernel<R, NW>;
     if (lds > 48 * 1024) {
         if (int s = check_hip(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "hipFuncSetAttribute(bwd_prepare)")) return s;
     }
+    const long long nsteps = batch * T;
     prof_begin(ctx, "affine_backward_prepare_operands");
-    hipLaunchKernelGGL(kern, dim3((unsigned)(batch * T)), dim3(256), lds, ctx->stream, static_cast<const c2 *>(A), static_cast<const c2 *>(H),
-                       static_cast<const R *>(G), static_cast<c2 *>(At), static_cast<c2 *>(gt), T, d);
+    hipLaunchKernelGGL(kern, dim3((unsigned)((nsteps + NW - 1) / NW)), dim3(NW * 64), lds, ctx->stream, static_cast<const c2 *>(A), static_cast<const c2 *>(H),
+                       static_cast<const R *>(G), static_cast<c2 *>(At), static_cast<c2 *>(gt), T, d, nsteps, direct);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch bwd_prepare_kernel");
+}
+
+// waves (steps) per workgroup: as many as the matrices' LDS tiles allow
+template <typename R> static int bwd_prepare_t(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d, long long batch)
+{
+    const size_t tile = (size_t)d * (d + 1) * 2 * sizeof(R);
+    if (4 * tile <= 64 * 1024) return bwd_prepare_launch<R, 4>(ctx, A, H, G, At, gt, T, d, batch);
+    if (2 * tile <= 96 * 1024) return bwd_prepare_launch<R, 2>(ctx, A, H, G, At, gt, T, d, batch);
+    return bwd_prepare_launch<R, 1>(ctx, A, H, G, At, gt, T, d, batch);
 }
 
 int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d,
