@@ -21,7 +21,9 @@
 // it owns, so that the operands of a 128 x 128 x 128 product are read once): a block whose outputs are all
 // certified ends there; one
 // with few outputs to repair hands them to its waves one at a time; only a block with many (float
-// components on wide-range data) runs the two sweeps over all sixteen positions per thread.
+// components on wide-range data) runs the two sweeps over all sixteen positions per thread, or, with float
+// components and at most 128 inner indices, orders the terms of every output first and finishes most outputs from
+// their one or two leading terms.
 #include <type_traits>
 
 #include "goom_chain_kernel.h"
@@ -37,6 +39,7 @@ struct ExactArgs {
     void *C;
     long long batch;
     int n, d, m;
+    float pos_inf; // +infinity
 };
 
 template <typename R> struct Num;
@@ -89,7 +92,14 @@ template <> __device__ inline double flip_sign<double>(double x, float signword)
     return __builtin_bit_cast(double, __builtin_bit_cast(unsigned long long, x) ^ ((unsigned long long)__builtin_bit_cast(unsigned, signword) << 32));
 }
 
-template <typename R> __global__ __launch_bounds__(kThreads, sizeof(R) == 4 ? 4 : 2) void lmme_exact_kernel(ExactArgs a)
+// KEYED (float components, at most 128 inner indices): a block with many outputs to repair orders the terms of
+// each by keys first and finishes most outputs from their one or two leading terms (see below); it then holds
+// all of its operands in LDS, which leaves room for two workgroups on a compute unit.
+constexpr int kKeyedMaxInner = 128;
+constexpr int kKeyedLda = kKeyedMaxInner + 1;
+constexpr size_t kKeyedLds = (size_t)kOut * kKeyedLda * 4 + (size_t)kKeyedMaxInner * kOut * 4 + 2 * kThreads * 4 + kOut * kOut * 2;
+
+template <typename R, bool KEYED> __global__ __launch_bounds__(kThreads, sizeof(R) == 4 && !KEYED ? 4 : 2) void lmme_exact_kernel(ExactArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int n = a.n, d = a.d, m = a.m;
@@ -108,16 +118,20 @@ template <typename R> __global__ __launch_bounds__(kThreads, sizeof(R) == 4 ? 4 
     const int blocks_k = (m + kSuper - 1) / kSuper, blocks_i = (n + kSuper - 1) / kSuper;
     // Workgroups go to the eight XCDs in turn, each with an L2 of its own: renumber them so that the blocks of
     // one batch item (which share rows of A' and columns of B') run on the same XCD, one after the other.
-    long long bid = blockIdx.x;
+    unsigned bid = blockIdx.x; // (the launcher keeps the grid below 2^31)
+    const unsigned per_item = (unsigned)blocks_i * (unsigned)blocks_k;
     {
-        const long long per_item = (long long)blocks_i * blocks_k, span = 8 * per_item;
-        if (bid < (long long)gridDim.x / span * span) {
-            const long long grp = bid / span, r = bid % span;
-            bid = (grp * 8 + r % 8) * per_item + r / 8;
+        const unsigned long long span = 8ull * per_item;
+        if (span <= gridDim.x) {
+            const unsigned sp = (unsigned)span;
+            if (bid < gridDim.x / sp * sp) {
+                const unsigned grp = bid / sp, r = bid % sp;
+                bid = (grp * 8 + r % 8) * per_item + r / 8;
+            }
         }
     }
-    const long long b = bid / ((long long)blocks_i * blocks_k);
-    const int rem = (int)(bid % ((long long)blocks_i * blocks_k));
+    const long long b = bid / per_item;
+    const int rem = (int)(bid % per_item);
     const int I0 = (rem / blocks_k) * kSuper, K0 = (rem % blocks_k) * kSuper;
     int i0 = I0, k0 = K0; // the block in hand
     const R *Ab = static_cast<const R *>(a.A) + (size_t)b * n * d * 2;
@@ -228,6 +242,17 @@ template <typename R> __global__ __launch_bounds__(kThreads, sizeof(R) == 4 ? 4 
     unsigned need = 0;
     R log2d = 0;
     for (int s = 1; s < d; s <<= 1) log2d += 1;
+    R cre[4][4]; // (all sixteen loads first, from addresses held inside the output, so that they are in flight together)
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int i = i0 + 4 * ty + r, k = k0 + 4 * tx + c;
+            if constexpr (KEYED) // (offsets of 32 bits: the launcher checks)
+                cre[r][c] = Cb[((unsigned)(i < n ? i : n - 1) * (unsigned)m + (unsigned)(k < m ? k : m - 1)) * 2u];
+            else
+                cre[r][c] = Cb[((size_t)(i < n ? i : n - 1) * m + (k < m ? k : m - 1)) * 2];
+        }
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -236,10 +261,9 @@ template <typename R> __global__ __launch_bounds__(kThreads, sizeof(R) == 4 ? 4 
             // (given shifts are whole numbers already, with -1e30 for a row or column without a finite entry)
             const R none = given ? (R)-1.0e29 : Num<R>::neg_inf();
             if (i < n && k < m && amax[r] > none && bmax[c] > none) {
-                const R cre = Cb[((size_t)i * m + k) * 2];
                 const R ni = given ? amax[r] : (R)__builtin_ceil((double)amax[r] * 1.44269504088896340736);
                 const R ek = given ? bmax[c] : (R)__builtin_ceil((double)bmax[c] * 1.44269504088896340736);
-                const R scaled = cre * Num<R>::kLog2e - ni - ek; // log2 of the scaled product's magnitude
+                const R scaled = cre[r][c] * Num<R>::kLog2e - ni - ek; // log2 of the scaled product's magnitude
                 if (!(scaled >= Num<R>::kMargin + log2d + 1)) need |= 1u << (4 * r + c); // also for -inf and NaN
             }
             // a zero row or column gives an exact zero either way
@@ -248,10 +272,22 @@ template <typename R> __global__ __launch_bounds__(kThreads, sizeof(R) == 4 ? 4 
     __syncthreads(); // (the block before this one is done with the list)
     if (tid == 0) s_count = 0;
     __syncthreads();
-    for (unsigned rest = need; rest != 0; rest &= rest - 1) {
-        const int q = __builtin_ctz(rest);
-        const int slot = atomicAdd(&s_count, 1);
-        if (slot < kMaxList) s_list[slot] = (4 * ty + q / 4) * kOut + 4 * tx + q % 4;
+    {   // (a wave reserves room for all of its lanes' outputs at once: one atomic a wave)
+        const int lane = tid & 63, mine = __builtin_popcount(need);
+        int before = mine; // inclusive prefix sum over the wave
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) {
+            const int o = __shfl_up(before, s, 64);
+            if (lane >= s) before += o;
+        }
+        int first = 0;
+        if (lane == 63 && before > 0) first = atomicAdd(&s_count, before);
+        first = __shfl(first, 63, 64);
+        int slot = first + before - mine;
+        for (unsigned rest = need; rest != 0 && slot < kMaxList; rest &= rest - 1, ++slot) {
+            const int q = __builtin_ctz(rest);
+            s_list[slot] = (4 * ty + q / 4) * kOut + 4 * tx + q % 4;
+        }
     }
     __syncthreads();
     const int count = s_count;
@@ -288,6 +324,215 @@ template <typename R> __global__ __launch_bounds__(kThreads, sizeof(R) == 4 ? 4 
         return;
     }
 
+    if constexpr (KEYED) {
+        // ---- many outputs to repair, float components on wide-range data: one or two terms decide most outputs,
+        // and the exponentials of all the others are work for nothing.  A first sweep orders the terms: every
+        // log-magnitude as a whole number of 1/16 units below the block's largest (at most 4096 units below: what
+        // is smaller counts as that, so a key never understates a term by more than the rounding), plus, for B',
+        // the inner index over 128 as a fraction.  Sums of such numbers are exact in float, so one addition gives
+        // a term's key, index included, and three more instructions keep the three largest keys of an output.  The
+        // operands themselves wait in registers meanwhile and then take the keys' place in LDS; the two leading
+        // terms are read back by index, and an output is finished from them when all other terms together,
+        // bounded through the third key, cannot move the result's last place.  What is left (about two per cent
+        // at N(0, 200^2)) is summed in full, an output to a lane.
+        constexpr int kHeld = kOut * kKeyedMaxInner / kThreads; // 32 entries of each operand to a thread
+        float *kx = reinterpret_cast<float *>(smem), *ky = kx + kOut * kKeyedLda; // keys, then the operands: [64][129], [128][64]
+        unsigned *sa = reinterpret_cast<unsigned *>(ky + kKeyedMaxInner * kOut), *sb = sa + kThreads; // signs, a word to a thread
+        unsigned short *open = reinterpret_cast<unsigned short *>(sb + kThreads);
+        float ablk = Num<float>::neg_inf(), bblk = Num<float>::neg_inf(); // upper bounds of the block's operands
+        {
+            const int lane = tid & 63;
+            const float av = blk_amax[lane], bv = blk_bmax[lane];
+            ablk = given ? (av > -1.0e29f ? av * Num<float>::kLn2 : Num<float>::neg_inf()) : av;
+            bblk = given ? (bv > -1.0e29f ? bv * Num<float>::kLn2 : Num<float>::neg_inf()) : bv;
+#pragma unroll
+            for (int s = 1; s < 64; s <<= 1) {
+                ablk = __builtin_fmaxf(ablk, __shfl_xor(ablk, s, 64));
+                bblk = __builtin_fmaxf(bblk, __shfl_xor(bblk, s, 64));
+            }
+        }
+        if (!(__builtin_fabsf(ablk) < 3.0e38f)) ablk = 0.0f; // (no finite entry, or an infinite one)
+        if (!(__builtin_fabsf(bblk) < 3.0e38f)) bblk = 0.0f;
+        constexpr float kPerUnit = 16.0f, kFloor = -4096.0f * 16.0f;
+        // NaN counts as the largest, so that the output is looked at and comes out as NaN
+        auto key_of = [&](float v, float top16) { return v == v ? __builtin_rintf(__builtin_amdgcn_fmed3f(__builtin_fmaf(v, kPerUnit, top16), kFloor, 0.0f)) : 0.0f; };
+        const float atop16 = -kPerUnit * ablk, btop16 = -kPerUnit * bblk;
+        struct Pair {
+            float re, im;
+        };
+        // entry u of a thread: A'[2 u + tid / 128][tid % 128] and B'[4 u + tid / 64][tid % 64] of the block, so that a
+        // wave reads 512 consecutive bytes at a time and a thread's entries lie a fixed stride apart.  The signs of a
+        // thread's 32 entries of an operand make one word (bit u), stored under the thread's number.
+        float ha[kHeld], hb[kHeld];
+        unsigned sign_a = 0, sign_b = 0;
+        const int ra0 = tid / kKeyedMaxInner, ja = tid % kKeyedMaxInner, jb0 = tid / kOut, cb = tid % kOut;
+        auto stage_operands = [&](auto whole) __attribute__((always_inline)) {
+            constexpr bool WHOLE = decltype(whole)::value; // the block lies inside the operands and d is 128: no edges
+            // (WHOLE: one address for the wave, which moves on from entry to entry, and a thread's 32-bit offset from it)
+            const float *base_a = Ab + (size_t)i0 * d * 2, *base_b = Bb + (size_t)k0 * 2;
+            const unsigned off_a = ((unsigned)ra0 * (unsigned)d + (unsigned)ja) * 2u, off_b = ((unsigned)jb0 * (unsigned)m + (unsigned)cb) * 2u;
+            const size_t step_a = (size_t)4 * d, step_b = (size_t)8 * m; // floats from one entry to the next
+#pragma unroll
+            for (int u0 = 0; u0 < kHeld; u0 += 16) {
+                Pair va[16], vb[16]; // sixteen loads of each in flight
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    if constexpr (WHOLE) {
+                        va[u] = *reinterpret_cast<const Pair *>(base_a + (u0 + u) * step_a + off_a);
+                        vb[u] = *reinterpret_cast<const Pair *>(base_b + (u0 + u) * step_b + off_b);
+                    } else { // (from addresses held inside the operands)
+                        const int r = 2 * (u0 + u) + ra0, jb = 4 * (u0 + u) + jb0;
+                        va[u] = *reinterpret_cast<const Pair *>(Ab + ((size_t)(i0 + r < n ? i0 + r : n - 1) * d + (ja < d ? ja : d - 1)) * 2);
+                        vb[u] = *reinterpret_cast<const Pair *>(Bb + ((size_t)(jb < d ? jb : d - 1) * m + (k0 + cb < m ? k0 + cb : m - 1)) * 2);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const int r = 2 * (u0 + u) + ra0, jb = 4 * (u0 + u) + jb0;
+                    const bool ina = WHOLE || (i0 + r < n && ja < d), inb = WHOLE || (k0 + cb < m && jb < d);
+                    const float xa = ina ? va[u].re : Num<float>::neg_inf(), xb = inb ? vb[u].re : Num<float>::neg_inf();
+                    ha[u0 + u] = xa;
+                    hb[u0 + u] = xb;
+                    kx[r * kKeyedLda + ja] = key_of(xa, atop16); // (-inf gets the lowest key)
+                    ky[jb * kOut + cb] = key_of(xb, btop16) + (float)jb * (1.0f / kKeyedMaxInner);
+                    sign_a |= (ina ? (unsigned)Num<float>::parity(va[u].im) : 0u) << (u0 + u);
+                    sign_b |= (inb ? (unsigned)Num<float>::parity(vb[u].im) : 0u) << (u0 + u);
+                }
+            }
+        };
+        if (d == kKeyedMaxInner && i0 + kOut <= n && k0 + kOut <= m)
+            stage_operands(std::true_type{});
+        else
+            stage_operands(std::false_type{});
+        sa[tid] = sign_a;
+        sb[tid] = sign_b;
+        __syncthreads();
+        float k1[4][4], k2[4][4], k3[4][4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) k1[r][c] = k2[r][c] = k3[r][c] = -3.0e6f;
+        // (The largest of two as a median with +inf, handed over as a kernel argument: one instruction, where the plain
+        // maximum would first put its operand in canonical form.)
+        const float inf = a.pos_inf;
+#pragma unroll 4
+        for (int j = 0; j < kKeyedMaxInner; ++j) {
+            float x[4], y[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) x[r] = kx[(4 * ty + r) * kKeyedLda + j];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) y[c] = ky[j * kOut + 4 * tx + c];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float key = x[r] + y[c];
+                    k3[r][c] = __builtin_amdgcn_fmed3f(k2[r][c], k3[r][c], key);
+                    k2[r][c] = __builtin_amdgcn_fmed3f(k1[r][c], k2[r][c], key);
+                    k1[r][c] = __builtin_amdgcn_fmed3f(k1[r][c], key, inf);
+                }
+        }
+        // ---- the operands in the keys' place
+        float *xf = kx, *yf = ky;
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < kHeld; ++u) {
+            xf[(2 * u + ra0) * kKeyedLda + ja] = ha[u];
+            yf[(4 * u + jb0) * kOut + cb] = hb[u];
+        }
+        if (tid == 0) s_count = 0;
+        __syncthreads();
+        // the two leading terms of every output, exactly, by the indices their keys carry
+        auto term = [&](int il, int kl, float key, float &t, unsigned &neg) {
+            const int j = (int)(key * (float)kKeyedMaxInner) & (kKeyedMaxInner - 1);
+            t = xf[il * kKeyedLda + j] + yf[j * kOut + kl];
+            neg = ((sa[(il % 2) * kKeyedMaxInner + j] >> (il / 2)) ^ (sb[(j % 4) * kOut + kl] >> (j / 4))) & 1u;
+        };
+        const float base = ablk + bblk;
+        // All d terms but the leading ones, each at most what the next key says, may be left out when together they
+        // move the result's logarithm by less than a quarter of its last place, |result| 2^-26: their share of the sum
+        // below that.  (A key understates its term by at most 1/16: two roundings to 1/32.)
+        const float slack0 = ::logf((float)d) + 0.07f + 26.0f * Num<float>::kLn2;
+        auto slack = [&](float result) { return slack0 - __builtin_amdgcn_logf(__builtin_fmaxf(__builtin_fabsf(result), 2.0f)) * Num<float>::kLn2; };
+        unsigned full = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float t1[4], t2[4];
+            unsigned s1[4], s2[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                term(4 * ty + r, 4 * tx + c, k1[r][c], t1[c], s1[c]);
+                term(4 * ty + r, 4 * tx + c, k2[r][c], t2[c], s2[c]);
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float b2 = k2[r][c] * (1.0f / kPerUnit) + base, b3 = k3[r][c] * (1.0f / kPerUnit) + base;
+                const float hi = __builtin_fmaxf(t1[c], t2[c]), lo = __builtin_fminf(t1[c], t2[c]);
+                const float e = __builtin_amdgcn_exp2f((lo - hi) * Num<float>::kLog2e); // in (0, 1]
+                const float w = s1[c] == s2[c] ? 1.0f + e : 1.0f - e;
+                const float both = hi + __builtin_amdgcn_logf(w) * Num<float>::kLn2; // (w is no denormal number that matters)
+                float re_out, im_out;
+                bool done = false;
+                if (b2 + slack(t1[c]) < t1[c]) { // one term decides
+                    re_out = t1[c];
+                    im_out = s1[c] ? Num<float>::pi() : 0.0f;
+                    done = true;
+                } else if (w > 0.0f && b3 + slack(both) < both) { // two terms decide, also after cancellation between them
+                    re_out = both;
+                    im_out = (t1[c] >= t2[c] ? s1[c] : s2[c]) ? Num<float>::pi() : 0.0f;
+                    done = true;
+                }
+                if (need & (1u << (4 * r + c))) {
+                    if (done) {
+                        *reinterpret_cast<Pair *>(Cb + ((size_t)(i0 + 4 * ty + r) * m + k0 + 4 * tx + c) * 2) = Pair{re_out, im_out};
+                    } else {
+                        full |= 1u << (4 * r + c);
+                    }
+                }
+            }
+        }
+        // the outputs still open, as a list: a wave reserves room for all of its lanes' at once
+        {
+            const int lane = tid & 63, mine = __builtin_popcount(full);
+            int before = mine; // inclusive prefix sum over the wave
+#pragma unroll
+            for (int s = 1; s < 64; s <<= 1) {
+                const int o = __shfl_up(before, s, 64);
+                if (lane >= s) before += o;
+            }
+            int first = 0;
+            if (lane == 63 && before > 0) first = atomicAdd(&s_count, before);
+            first = __shfl(first, 63, 64);
+            int slot = first + before - mine;
+            for (unsigned rest = full; rest != 0; rest &= rest - 1) {
+                const int q = __builtin_ctz(rest);
+                open[slot++] = (unsigned short)((4 * ty + q / 4) * kOut + 4 * tx + q % 4);
+            }
+        }
+        __syncthreads();
+        const int nopen = s_count;
+        // ---- a lane takes one of them and walks the inner index twice (largest term, then the sum)
+        for (int e = tid; e < nopen; e += kThreads) {
+            const int il = open[e] / kOut, kl = open[e] % kOut;
+            const float *xr = xf + il * kKeyedLda, *yc = yf + kl;
+            float zmax = Num<float>::neg_inf();
+#pragma unroll 8
+            for (int j = 0; j < kKeyedMaxInner; ++j) zmax = __builtin_fmaxf(zmax, xr[j] + yc[j * kOut]);
+            const float scale = zmax > Num<float>::neg_inf() ? -(zmax * Num<float>::kLog2e) : 0.0f;
+            float sv = 0.0f;
+            const unsigned *sar = sa + (il % 2) * kKeyedMaxInner, *sbc = sb + kl;
+#pragma unroll 8
+            for (int j = 0; j < kKeyedMaxInner; ++j) {
+                const float t = Num<float>::exp2_(Num<float>::fma_(xr[j] + yc[j * kOut], Num<float>::kLog2e, scale));
+                const unsigned flip = ((sar[j] >> (il / 2)) ^ (sbc[(j % 4) * kOut] >> (j / 4))) << 31;
+                sv += __builtin_bit_cast(float, __builtin_bit_cast(unsigned, t) ^ flip);
+            }
+            float *out = Cb + ((size_t)(i0 + il) * m + k0 + kl) * 2;
+            *reinterpret_cast<Pair *>(out) = Pair{sv != 0.0f ? (::log2f(__builtin_fabsf(sv)) - scale) * Num<float>::kLn2 : Num<float>::neg_inf(),
+                                                  sv < 0.0f ? Num<float>::pi() : 0.0f};
+        }
+        return;
+    }
     // ---- many outputs to repair: first the largest pairwise sum of every output of the block ...
     R mx[4][4];
 #pragma unroll
@@ -413,20 +658,27 @@ int launch_lmme_exact(goom_ctx *ctx, const void *A, const void *B, void *C, long
     a.n = n;
     a.d = d;
     a.m = m;
+    a.pos_inf = __builtin_huge_valf();
     const int sup = dtype == GOOM_C64 ? super_block<float>() : super_block<double>();
     const long long grid = batch * ((n + sup - 1) / sup) * ((m + sup - 1) / sup);
     if (grid > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many output blocks for one launch");
     const size_t comp = dtype == GOOM_C64 ? 4 : 8;
-    const size_t lds = (size_t)kOut * (kJBlock + 1) * (comp + 4) + (size_t)kJBlock * kOut * (comp + 4) + 64;
+    const bool keyed = dtype == GOOM_C64 && d <= kKeyedMaxInner && (long long)n * m < (1LL << 28);
+    size_t lds = (size_t)kOut * (kJBlock + 1) * (comp + 4) + (size_t)kJBlock * kOut * (comp + 4) + 64;
+    if (keyed && lds < kKeyedLds) lds = kKeyedLds;
+    const void *kern = dtype != GOOM_C64 ? reinterpret_cast<const void *>(lmme_exact_kernel<double, false>)
+                       : keyed           ? reinterpret_cast<const void *>(lmme_exact_kernel<float, true>)
+                                         : reinterpret_cast<const void *>(lmme_exact_kernel<float, false>);
     if (lds > 48 * 1024) {
-        const void *kern = dtype == GOOM_C64 ? reinterpret_cast<const void *>(lmme_exact_kernel<float>) : reinterpret_cast<const void *>(lmme_exact_kernel<double>);
         if (int st = check_hip(ctx, hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "hipFuncSetAttribute(lmme_exact_kernel)")) return st;
     }
     prof_begin(ctx, "lmme_exact_repair");
-    if (dtype == GOOM_C64)
-        hipLaunchKernelGGL(lmme_exact_kernel<float>, dim3((unsigned)grid), dim3(kThreads), lds, ctx->stream, a);
+    if (dtype != GOOM_C64)
+        hipLaunchKernelGGL((lmme_exact_kernel<double, false>), dim3((unsigned)grid), dim3(kThreads), lds, ctx->stream, a);
+    else if (keyed)
+        hipLaunchKernelGGL((lmme_exact_kernel<float, true>), dim3((unsigned)grid), dim3(kThreads), lds, ctx->stream, a);
     else
-        hipLaunchKernelGGL(lmme_exact_kernel<double>, dim3((unsigned)grid), dim3(kThreads), lds, ctx->stream, a);
+        hipLaunchKernelGGL((lmme_exact_kernel<float, false>), dim3((unsigned)grid), dim3(kThreads), lds, ctx->stream, a);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch lmme_exact_kernel");
 }

@@ -263,6 +263,46 @@ def test_lmme_partly_repaired_blocks(G, oracle, sigma):
     compare(got, re, sg, kap, name=f"lmme sigma {sigma}", max_ill_fraction=0.002)
 
 
+def test_lmme_repair_when_few_terms_decide(G, oracle):
+    # float repair pass, the outputs that one or two terms decide: log-magnitudes +300 (rarely) or -300, so that
+    # the largest pairwise sums are exactly 0 (ties among them, and a key whose number part is zero) or 600, far
+    # above all others; then ragged sizes with more than 128 inner indices, zeros among the entries, and one
+    # row / column pair that cancels exactly in its two leading terms
+    from paper_2510_03426_amd import LMME_EXACT
+    rng = np.random.default_rng(si.BASE_SEED + 270)
+    b, n, d, m = 2, 128, 128, 128
+    A = np.empty((b, n, d), np.complex64)
+    B = np.empty((b, d, m), np.complex64)
+    A.real = np.where(rng.random((b, n, d)) < 0.02, 300.0, -300.0)
+    B.real = np.where(rng.random((b, d, m)) < 0.02, 300.0, -300.0)
+    A.imag = np.float32(np.pi) * rng.integers(0, 2, (b, n, d))
+    B.imag = np.float32(np.pi) * rng.integers(0, 2, (b, d, m))
+    re, sg, kap = oracle.lmme(A, B, return_kappa=True)
+    got = host(G.lmme(dev(A), dev(B), flags=LMME_EXACT))
+    say(f"lmme two-valued: outputs at 600 {np.mean(re > 500):.1%}, near 0 {np.mean(np.abs(re) < 50):.1%}, zero or below {np.mean(re < -500):.1%}")
+    compare(got, re, sg, kap, name="lmme two-valued", max_ill_fraction=0.25)
+    b, n, d, m = 2, 70, 200, 90
+    A, B = si.wide_range_goom_pairs(si.BASE_SEED + 271, b, n, d, m, sigma=200.0, dtype=np.complex64)
+    A.real[rng.random(A.shape) < 0.3] = -np.inf
+    B.real[rng.random(B.shape) < 0.3] = -np.inf
+    A.real[:, 5, :] = -np.inf  # a zero row: zeros out
+    A.real[0, 7, :] = -np.inf  # one term alone
+    A.real[0, 7, 150] = 12.5
+    re, sg, kap = oracle.lmme(A, B, return_kappa=True)
+    got = host(G.lmme(dev(A), dev(B), flags=LMME_EXACT))
+    assert np.isneginf(got.real[:, 5, :]).all()
+    compare(got, re, sg, kap, name="lmme ragged with zeros", max_ill_fraction=0.01)
+    # two leading terms of opposite sign, half a unit apart: inner indices 0 and 1 tower over the others
+    A2, B2 = A[:1].copy(), B[:1].copy()
+    A2[0, :, 0] = 900.0
+    A2[0, :, 1] = 899.5 + 1j * np.float32(np.pi)
+    B2[0, 1, :] = B2[0, 0, :]
+    B2.real[0, 0:2, :] = np.where(np.isneginf(B2.real[0, 0:2, :]), 0.0, B2.real[0, 0:2, :])
+    re, sg, kap = oracle.lmme(A2, B2, return_kappa=True)
+    got = host(G.lmme(dev(A2), dev(B2), flags=LMME_EXACT))
+    compare(got, re, sg, kap, name="lmme two leading terms of opposite sign", max_ill_fraction=0.01)
+
+
 # -------------------------------------------------------------------------------- scan
 
 def run_scan_case(G, oracle, T, d, chunk_len, m=None, batch=1, seed=0, dtype=np.float32, name=""):
