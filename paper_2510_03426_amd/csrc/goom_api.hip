@@ -1210,10 +1210,10 @@ int goom_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, 
 size_t goom_lyapunov_spectrum_per_step_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts,
                                                        int caller_has_states, int caller_has_step_logs)
 {
-    if (T <= 0 || d <= 0 || batch <= 0 || d > 64 || dtype != GOOM_C64) return 0;
+    if (T <= 0 || d <= 0 || batch <= 0 || d > 64 || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
     const ResetPlan p = plan_reset(T, d, batch, dtype, opts);
     size_t n = p.total() + lyap_steps_partial_bytes(batch, d);
-    if (!caller_has_states) n += align_up((size_t)batch * T * d * d * 8, 256);
+    if (!caller_has_states) n += align_up((size_t)batch * T * d * d * 2 * comp_bytes(dtype), 256);
     if (!caller_has_step_logs) n += align_up((size_t)batch * T * d * sizeof(double), 256);
     return n;
 }
@@ -1226,7 +1226,6 @@ int goom_lyapunov_spectrum_per_step(goom_ctx *ctx, const void *J, const void *S0
     if (!lambda || !J) return fail(ctx, GOOM_EINVAL, "null data pointer");
     if (!(dt > 0.0)) return fail(ctx, GOOM_EINVAL, "dt must be positive");
     if (T <= 0 || batch <= 0 || d <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive (T=%lld d=%d batch=%lld)", (long long)T, d, (long long)batch);
-    if (dtype != GOOM_C64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan is built for GOOM_C64 only");
     if (d > 64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 64 (d=%d)", d);
     if (step_logs && !aligned(step_logs, 8)) return fail(ctx, GOOM_EINVAL, "step_logs must be 8-byte aligned");
     const size_t need = goom_lyapunov_spectrum_per_step_workspace_bytes(T, d, batch, dtype, opts, states != nullptr, step_logs != nullptr);
@@ -1237,13 +1236,13 @@ int goom_lyapunov_spectrum_per_step(goom_ctx *ctx, const void *J, const void *S0
     w += lyap_steps_partial_bytes(batch, d);
     if (!states) {
         states = w;
-        w += align_up((size_t)batch * T * d * d * 8, 256);
+        w += align_up((size_t)batch * T * d * d * 2 * comp_bytes(dtype), 256);
     }
     if (!step_logs) step_logs = reinterpret_cast<double *>(w);
     // group (a): all states, selectively reset
     if (int s = run_reset(ctx, J, S0, states, nullptr, nullptr, 1.0, T, d, batch, dtype, opts, workspace, p.total())) return s;
     // groups (b)-(d)
-    return launch_lyap_steps(ctx, J, S0, states, step_logs, partial, lambda, T, d, batch, 1.0 / (dt * (double)T));
+    return launch_lyap_steps(ctx, J, S0, states, step_logs, partial, lambda, T, d, batch, dtype, 1.0 / (dt * (double)T));
 }
 
 size_t goom_largest_lyapunov_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts)

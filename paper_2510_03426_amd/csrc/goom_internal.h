@@ -126,7 +126,7 @@ size_t reset_tree_workspace_bytes(long long T, int d, long long batch, int dtype
 int run_reset_tree(goom_ctx *ctx, const void *J, const void *S0, void *states, unsigned char *out_flags, long long T, int d, long long batch,
                    int dtype, int policy, float cos_threshold, void *ws);
 int launch_lyap_steps(goom_ctx *ctx, const void *J, const void *S0, const void *states, double *steplog, double *partial,
-                      double *lambda, long long T, int d, long long batch, double scale);
+                      double *lambda, long long T, int d, long long batch, int dtype, double scale);
 size_t lyap_steps_partial_bytes(long long batch, int d);
 int launch_lle_epilogue(goom_ctx *ctx, const void *v, double *lle, long long batch, int d, int dtype, double scale);
 int launch_uniform_u0(goom_ctx *ctx, void *u, long long batch, int d, int dtype);

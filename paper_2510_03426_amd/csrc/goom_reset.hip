@@ -957,6 +957,132 @@ template <int DP> __global__ __launch_bounds__(64) void lyap_step_kernel(StepArg
     }
 }
 
+// The same for complex128 GOOMs, in double throughout: the factorisations and the product run on the double matrix
+// instruction in the layout of the carry kernel above (register v of lane (g, c) holds row 4 v + g; whatever is read
+// from LDS as a four-vector stores index 4 v + g at position 4 g + v).
+struct StepArgsD {
+    const double *J, *S0, *states;
+    double *steplog;
+    long long T;
+    int d;
+};
+
+template <int DP> __global__ __launch_bounds__(64) void lyap_step_kernel_d(StepArgsD a)
+{
+    constexpr int KT = DP / 16;
+    constexpr int LDT = WaveD<DP>::LDT;
+    constexpr int TQ = DP * DP / 4 / 64;
+    __shared__ __align__(32) WaveD<DP> s;
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, c = lane & 15;
+    const int d = a.d;
+    const long long b = blockIdx.x / a.T, t = blockIdx.x % a.T;
+    auto is_odd = [](double im) { return ((int)rint(im * 0.318309886183790671538) & 1) != 0; };
+
+    // ---- input state, columns scaled to largest entry 1 (identity block past d)
+    const double *src = t == 0 ? (a.S0 ? a.S0 + (size_t)b * d * d * 2 : nullptr) : a.states + (size_t)(b * a.T + t - 1) * d * d * 2;
+    d4 Q[KT][KT];
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) {
+        const int col = 16 * nt + c;
+        double cmax = -__builtin_huge_val();
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * mt + 4 * v + g;
+                double r = row == col ? 0.0 : -__builtin_huge_val();
+                if (src && row < d && col < d) r = src[((size_t)row * d + col) * 2];
+                Q[nt][mt][v] = r;
+                cmax = fmax(cmax, r);
+            }
+        cmax = fmax(cmax, __shfl_xor(cmax, 16, 64));
+        cmax = fmax(cmax, __shfl_xor(cmax, 32, 64));
+        const bool zero_col = !(cmax > -__builtin_huge_val());
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * mt + 4 * v + g;
+                const double tt = (Q[nt][mt][v] - cmax) * kLog2e;
+                double x = (zero_col || !(tt > -1000.0)) ? 0.0 : exp2(tt);
+                if (src && row < d && col < d && is_odd(src[((size_t)row * d + col) * 2 + 1])) x = -x;
+                Q[nt][mt][v] = x;
+            }
+    }
+    {
+        double piv[KT], ce[KT];
+        const double amp = qr_panels_d<DP>(Q, piv, ce, s, g, c);
+        if (amp > 1.0e3) (void)qr_panels_d<DP>(Q, piv, ce, s, g, c);
+    }
+
+    // ---- J_t as reals scaled by 2^-sh, sh from the largest entry; identity block past d
+    const double *jp = a.J + (size_t)(b * a.T + t) * d * d * 2;
+    double jmax = -__builtin_huge_val();
+    for (int q = 0; q < TQ; ++q) {
+        const int piece = lane + 64 * q;
+        const int row = piece / (DP / 4), c4 = 4 * (piece % (DP / 4));
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (row < d && c4 + e < d) jmax = fmax(jmax, jp[((size_t)row * d + c4 + e) * 2]);
+    }
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) jmax = fmax(jmax, __shfl_xor(jmax, sft, 64));
+    const double sh = jmax > -__builtin_huge_val() ? ceil(jmax * kLog2e) : 0.0;
+    for (int q = 0; q < TQ; ++q) {
+        const int piece = lane + 64 * q;
+        const int row = piece / (DP / 4), c4 = 4 * (piece % (DP / 4));
+        const int p4 = (c4 & ~15) | ((c4 >> 2) & 3);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            double x = (c4 + e == row) ? 1.0 : 0.0;
+            if (row < d && c4 + e < d) {
+                const double *v = jp + ((size_t)row * d + c4 + e) * 2;
+                const double tt = __builtin_fma(v[0], kLog2e, -sh);
+                x = tt > -1000.0 ? exp2(tt) : 0.0;
+                if (is_odd(v[1])) x = -x;
+            }
+            s.tile[row * LDT + p4 + 4 * e] = x;
+        }
+    }
+    wave_sync();
+    d4 Z[KT][KT];
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) Z[nt][mt] = d4{0., 0., 0., 0.};
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) {
+            const d4 av = *reinterpret_cast<const d4 *>(&s.tile[(16 * mt + c) * LDT + 16 * kt + 4 * g]);
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int nt = 0; nt < KT; ++nt) Z[nt][mt] = mfma8(av[v], Q[nt][kt][v], Z[nt][mt]);
+        }
+    wave_sync();
+    double piv[KT], piv2[KT], ce[KT], ce2[KT];
+    const double amp = qr_panels_d<DP>(Z, piv, ce, s, g, c);
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) {
+        piv2[nt] = 1.0;
+        ce2[nt] = 0.0;
+    }
+    if (amp > 1.0e3) (void)qr_panels_d<DP>(Z, piv2, ce2, s, g, c);
+    if (g == 0) {
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt) {
+            const int col = 16 * nt + c;
+            if (col < d) {
+                const bool ok = piv[nt] > 1.0e-280 && piv2[nt] > 1.0e-280;
+                a.steplog[(size_t)(b * a.T + t) * d + col] =
+                    ok ? 0.5 * (log(piv[nt]) + log(piv2[nt])) + (ce[nt] + ce2[nt] + sh) * kLn2 : -__builtin_huge_val();
+            }
+        }
+    }
+}
+
 // lambda[b][k] = scale * sum_t steplog[b][t][k], summed in a fixed order: kSlices slices of the
 // steps per batch item, partial sums in the workspace, then one block adds the slices.
 constexpr int kSlices = 64;
@@ -1084,27 +1210,42 @@ int launch_reset_post(goom_ctx *ctx, const ResetLaunch &l)
 
 
 int launch_lyap_steps(goom_ctx *ctx, const void *J, const void *S0, const void *states, double *steplog, double *partial,
-                      double *lambda, long long T, int d, long long batch, double scale)
+                      double *lambda, long long T, int d, long long batch, int dtype, double scale)
 {
-    StepArgs a;
-    a.J = static_cast<const float *>(J);
-    a.S0 = static_cast<const float *>(S0);
-    a.states = static_cast<const float *>(states);
-    a.steplog = steplog;
-    a.T = T;
-    a.d = d;
     const long long grid = batch * T;
     if (grid > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
     const int dp = padded_dim(d);
+    if (dp > 64) return fail(ctx, GOOM_EUNSUPPORTED, "the per-step estimator supports d <= 64 (d=%d)", d);
     prof_begin(ctx, "lyapunov_per_step_qr");
-    if (dp == 16)
-        hipLaunchKernelGGL(lyap_step_kernel<16>, dim3((unsigned)grid), dim3(64), 0, ctx->stream, a);
-    else if (dp == 32)
-        hipLaunchKernelGGL(lyap_step_kernel<32>, dim3((unsigned)grid), dim3(64), 0, ctx->stream, a);
-    else if (dp == 64)
-        hipLaunchKernelGGL(lyap_step_kernel<64>, dim3((unsigned)grid), dim3(64), 0, ctx->stream, a);
-    else
-        return fail(ctx, GOOM_EUNSUPPORTED, "the per-step estimator supports d <= 64 (d=%d)", d);
+    if (dtype == GOOM_C64) {
+        StepArgs a;
+        a.J = static_cast<const float *>(J);
+        a.S0 = static_cast<const float *>(S0);
+        a.states = static_cast<const float *>(states);
+        a.steplog = steplog;
+        a.T = T;
+        a.d = d;
+        if (dp == 16)
+            hipLaunchKernelGGL(lyap_step_kernel<16>, dim3((unsigned)grid), dim3(64), 0, ctx->stream, a);
+        else if (dp == 32)
+            hipLaunchKernelGGL(lyap_step_kernel<32>, dim3((unsigned)grid), dim3(64), 0, ctx->stream, a);
+        else
+            hipLaunchKernelGGL(lyap_step_kernel<64>, dim3((unsigned)grid), dim3(64), 0, ctx->stream, a);
+    } else {
+        StepArgsD a;
+        a.J = static_cast<const double *>(J);
+        a.S0 = static_cast<const double *>(S0);
+        a.states = static_cast<const double *>(states);
+        a.steplog = steplog;
+        a.T = T;
+        a.d = d;
+        if (dp == 16)
+            hipLaunchKernelGGL(lyap_step_kernel_d<16>, dim3((unsigned)grid), dim3(64), 0, ctx->stream, a);
+        else if (dp == 32)
+            hipLaunchKernelGGL(lyap_step_kernel_d<32>, dim3((unsigned)grid), dim3(64), 0, ctx->stream, a);
+        else
+            hipLaunchKernelGGL(lyap_step_kernel_d<64>, dim3((unsigned)grid), dim3(64), 0, ctx->stream, a);
+    }
     prof_end(ctx);
     if (int st = check_hip(ctx, hipGetLastError(), "launch lyap_step_kernel")) return st;
     prof_begin(ctx, "lyapunov_mean_of_logs");

@@ -654,13 +654,18 @@ def test_lyapunov_spectrum_gaussian_closed_form(G, oracle):
 
 # ------------------------------------ per-step estimator and largest exponent (Sections 4.2.1-4.2.2)
 
-@pytest.mark.parametrize("T,d,L,policy", [(2048, 32, 0, 1), (1000, 8, 16, 1), (600, 16, 7, 0), (300, 64, 16, 1)])
-def test_lyapunov_per_step_estimator(G, oracle, T, d, L, policy):
+@pytest.mark.parametrize("T,d,L,policy,ctype", [(2048, 32, 0, 1, np.complex64), (1000, 8, 16, 1, np.complex64), (600, 16, 7, 0, np.complex64),
+                                                (300, 64, 16, 1, np.complex64), (1500, 32, 0, 1, np.complex128), (400, 10, 9, 0, np.complex128),
+                                                (200, 64, 16, 1, np.complex128)])
+def test_lyapunov_per_step_estimator(G, oracle, T, d, L, policy, ctype):
     # groups (b)-(d): two QRs per step on the selectively reset states; against the same groups in the
     # oracle (fed the oracle's own states) and against the sequential QR method
     dt = 0.01
     Jr = lorenz_chain(T, d, 71, burn_in=3000)
+    if ctype == np.complex128:
+        Jr = Jr.astype(np.float64)
     Jz = oracle.to_goom(Jr)
+    assert Jz.dtype == ctype
     check = L if L > 0 else 32
     re, sg, _, _ = oracle.reset_scan(Jz, None, check_every=check, policy=policy)
     eye_re = np.where(np.eye(d) > 0, 0.0, -np.inf)
@@ -669,13 +674,14 @@ def test_lyapunov_per_step_estimator(G, oracle, T, d, L, policy):
     lam_qr = oracle.lyapunov_qr(Jr, dt)
     lam, logs = G.lyapunov_spectrum_per_step(dev(Jz), dt, chunk_len=L, policy=policy, want_step_logs=True)
     lam, logs = host(lam), host(logs)
-    say(f"per-step estimator T={T} d={d} L={L or 'default'} policy={policy}: max |gpu - oracle groups| = "
+    say(f"per-step estimator {np.dtype(ctype).name} T={T} d={d} L={L or 'default'} policy={policy}: max |gpu - oracle groups| = "
         f"{np.abs(lam - lam_ref).max():.2e}, max |gpu - QR method| = {np.abs(lam - lam_qr).max():.2e}, "
         f"worst single log R_kk off by {np.abs(logs - logs_ref).max():.2e}")
-    assert np.abs(lam - lam_ref).max() < 1e-3 and np.abs(lam - lam_qr).max() < 1e-3
+    tol = 1e-3 if ctype == np.complex64 else 1e-7
+    assert np.abs(lam - lam_ref).max() < tol and np.abs(lam - lam_qr).max() < 1e-3
     # per step the logs add up to log|det J_t| whatever the basis; float QR keeps that to about 1e-4
     dets = np.array([np.linalg.slogdet(j.astype(np.float64))[1] for j in Jr])
-    assert np.abs(logs.sum(axis=1) - dets).max() < 2e-3
+    assert np.abs(logs.sum(axis=1) - dets).max() < (2e-3 if ctype == np.complex64 else 1e-9)
     # and the estimator that accumulates growth at the resets agrees
     lam2 = host(G.lyapunov_spectrum(dev(Jz), dt, chunk_len=L, policy=1))
     assert np.abs(lam - lam2).max() < 1e-3
