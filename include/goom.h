@@ -384,8 +384,9 @@ int goom_from_goom_backward(goom_ctx *ctx, const void *y, const void *grad_x, vo
  * a value lies within eps of zero; a state entry that is exactly zero passes no gradient.
  * A, bias, h0 (NULL = zero), H: as given to and returned by goom_affine_scan; grad_H: [batch, T, d] reals;
  * grad_A: [batch, T, d, d] reals; grad_bias: NULL or [batch, T, d] reals; grad_h0: NULL or [batch, d] reals (needs
- * h0).  opts->flags must be 0.  workspace: goom_affine_scan_backward_workspace_bytes(...) bytes: it holds the
- * transposed copy of A, so it is a little larger than A itself. */
+ * h0).  opts->flags must be 0.  workspace: goom_affine_scan_backward_workspace_bytes(...) bytes: a few vectors per
+ * step for complex64 with d = 16 or 32 and more than one chunk (the scan reads A transposed itself); otherwise it
+ * also holds a transposed copy of A and is a little larger than A. */
 int goom_affine_scan_backward(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H,
                               const void *grad_H, void *grad_A, void *grad_bias, void *grad_h0, int64_t T, int d,
                               int64_t batch, int dtype, const goom_scan_opts *opts, void *workspace,

@@ -34,7 +34,10 @@ constexpr int kWalkWaves = 4; // chunks per workgroup
 // are handled per pass and the work that is done once per row (its shift, the bias, the new
 // exponent) is repeated by few lanes.  Outputs leave through the transposed vector: after its trip
 // through LDS lane i < d holds entry i and one store instruction writes the whole state.
-template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk_kernel(ChainArgs a, long long nchains)
+// ADJ: the adjoint recurrence's factors, read from the forward pass's matrices: step s takes the transpose of matrix
+// steps - s (eight 8-byte loads a pass instead of four 16-byte ones; a load instruction of the wave still covers
+// whole 128-byte lines) and adds left_shift[s] to its log-magnitudes.
+template <int DP, bool TI, bool ADJ = false> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk_kernel(ChainArgs a, long long nchains)
 {
     typedef Comp<float> C;
     constexpr int EPL = DP >= 32 ? 8 : 4; // entries of a row per lane
@@ -110,13 +113,32 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
 
     f4 cur[Q][NV], nxt[Q][NV];
     float2 bcur[Q], bnxt[Q];
-    auto load_matrix = [&](long long t, f4 (&it)[Q][NV]) {
-        const unsigned char *src = left0 + t * a.left_step_stride;
+    [[maybe_unused]] float shift_cur = 0.0f, shift_nxt = 0.0f;
+    [[maybe_unused]] const unsigned char *adj0 = a.left + item * a.left_batch_stride;
+    [[maybe_unused]] const float *shift0 = ADJ ? a.left_shift + item * a.steps : nullptr;
+    [[maybe_unused]] const unsigned adj_off = (unsigned)(c0 * DP + rsub) * 8u; // bytes: entry (c0, rsub) of the source matrix
+    auto load_matrix = [&](long long t, f4 (&it)[Q][NV], float &shift) {
+        if constexpr (ADJ) {
+            const long long s = t0 + t, k = s > 0 ? a.steps - s : a.steps - 1; // (step 0: any matrix, shifted to nothing)
+            const unsigned char *src = adj0 + k * a.left_step_stride;
+            shift = shift0[s];
 #pragma unroll
-        for (int q = 0; q < Q; ++q)
+            for (int q = 0; q < Q; ++q)
 #pragma unroll
-            for (int v = 0; v < NV; ++v)
-                it[q][v] = *reinterpret_cast<const f4 *>(src + (mat_off + (unsigned)(q * RPP * DP * 8 + 16 * v)));
+                for (int v = 0; v < NV; ++v) {
+                    // entries (row, c0 + 2 v) and (row, c0 + 2 v + 1) of the transpose, row = q RPP + rsub
+                    const float2 x = *reinterpret_cast<const float2 *>(src + (adj_off + (unsigned)(((2 * v) * DP + q * RPP) * 8)));
+                    const float2 y = *reinterpret_cast<const float2 *>(src + (adj_off + (unsigned)(((2 * v + 1) * DP + q * RPP) * 8)));
+                    it[q][v] = f4{x.x, x.y, y.x, y.y};
+                }
+        } else {
+            const unsigned char *src = left0 + t * a.left_step_stride;
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+#pragma unroll
+                for (int v = 0; v < NV; ++v)
+                    it[q][v] = *reinterpret_cast<const f4 *>(src + (mat_off + (unsigned)(q * RPP * DP * 8 + 16 * v)));
+        }
     };
     auto load_bias = [&](long long t, float2 (&bb)[Q]) {
         const unsigned char *bsrc = bias0 + (size_t)t * DP * 8;
@@ -127,15 +149,15 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
     const float kLo = 1.925963033500011e-8f;      // log2(e) - kHi
     // the lane's entries of every row, scaled by the row's power of two and signed; the row shifts
     float sv[Q][EPL], nrow[Q];
-    auto scale_rows = [&](const f4 (&it)[Q][NV]) {
+    auto scale_rows = [&](const f4 (&it)[Q][NV], float shift) {
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             float re[EPL], im[EPL];
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
-                re[2 * v] = it[q][v][0];
+                re[2 * v] = ADJ ? it[q][v][0] + shift : it[q][v][0];
                 im[2 * v] = it[q][v][1];
-                re[2 * v + 1] = it[q][v][2];
+                re[2 * v + 1] = ADJ ? it[q][v][2] + shift : it[q][v][2];
                 im[2 * v + 1] = it[q][v][3];
             }
             // row shift: a whole number near the row's largest log2|A_ij|
@@ -168,9 +190,9 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
             }
         }
     };
-    load_matrix(0, cur);
+    load_matrix(0, cur, shift_cur);
     load_bias(0, bcur);
-    if (TI) scale_rows(cur);
+    if (TI) scale_rows(cur, 0.0f);
 
     // A step's outputs are stored at the top of the next step, behind that step's loads: the wait for
     // those loads then finds the stores a whole step old, not just issued (loads and stores share
@@ -184,10 +206,10 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
     };
     for (long long t = 0; t < len; ++t) {
         const long long tn = t + 1 < len ? t + 1 : len - 1;
-        if (!TI) load_matrix(tn, nxt);
+        if (!TI) load_matrix(tn, nxt, shift_nxt);
         load_bias(tn, bnxt);
         if (t > 0) store_outputs(t - 1);
-        if (!TI) scale_rows(cur);
+        if (!TI) scale_rows(cur, shift_cur);
         if (vec_zero) {
             // a zero vector has no scale of its own: it takes the bias's, whatever its magnitude (an adjoint
             // recurrence starts at e^-1000 and below), instead of flushing the bias on the scale 2^0
@@ -283,6 +305,7 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
                 if (!TI) cur[q][v] = nxt[q][v];
             bcur[q] = bnxt[q];
         }
+        shift_cur = shift_nxt;
     }
     store_outputs(len - 1);
 
@@ -319,7 +342,8 @@ template <int DP, bool TI> __global__ __launch_bounds__(kWalkWaves * 64) void af
 // a.bias == NULL: no bias is added (the column stays zero), which gives plain matrix powers and products.
 // PRECISE: every entry of the tile is exponentiated in double and rounded once (for one matrix applied at every
 // step, whose conversion error would otherwise be the same at every step and add up along the chain).
-template <int DP, int NW, bool PRECISE>
+// ADJ: as in the matrix-vector walk above (the factor of step s is the transpose of matrix steps - s, shifted).
+template <int DP, int NW, bool PRECISE, bool ADJ = false>
 __global__ __launch_bounds__((NW + 1) * 64, 4) void affine_chunk_f64_kernel(ChainArgs a)
 {
     typedef Comp<float> C;
@@ -367,14 +391,32 @@ __global__ __launch_bounds__((NW + 1) * 64, 4) void affine_chunk_f64_kernel(Chai
     const long long chain_global = item * a.chunks_per_item + chunk;
     const unsigned char *left0 = a.left + item * a.left_batch_stride + t0 * a.left_step_stride;
 
+    [[maybe_unused]] const unsigned char *adj0 = a.left + item * a.left_batch_stride;
+    [[maybe_unused]] const float *shift0 = ADJ ? a.left_shift + item * a.steps : nullptr;
+    [[maybe_unused]] float pre_shift = 0.0f; // the shift of the step whose entries wait in `pre`
     auto load_items = [&](long long t, Item4 (&it)[Q]) {
-        const float *src = reinterpret_cast<const float *>(left0 + t * a.left_step_stride);
+        if constexpr (ADJ) {
+            const long long s = t0 + t, k = s > 0 ? a.steps - s : a.steps - 1; // (step 0: any matrix, shifted to nothing)
+            const float *src = reinterpret_cast<const float *>(adj0 + k * a.left_step_stride);
+            pre_shift = shift0[s];
 #pragma unroll
-        for (int q = 0; q < Q; ++q) {
-            const int row = (tid + q * NT) / LPR;
-            const f4 *gp = reinterpret_cast<const f4 *>(src + ((size_t)row * DP + c4) * 2);
-            it[q].a = gp[0];
-            it[q].b = gp[1];
+            for (int q = 0; q < Q; ++q) {
+                const int row = (tid + q * NT) / LPR; // entries (row, c4 .. c4 + 3) of the transpose
+                float2 x[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = *reinterpret_cast<const float2 *>(src + ((size_t)(c4 + e) * DP + row) * 2);
+                it[q].a = f4{x[0].x, x[0].y, x[1].x, x[1].y};
+                it[q].b = f4{x[2].x, x[2].y, x[3].x, x[3].y};
+            }
+        } else {
+            const float *src = reinterpret_cast<const float *>(left0 + t * a.left_step_stride);
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int row = (tid + q * NT) / LPR;
+                const f4 *gp = reinterpret_cast<const f4 *>(src + ((size_t)row * DP + c4) * 2);
+                it[q].a = gp[0];
+                it[q].b = gp[1];
+            }
         }
     };
     // tile[i][phys(j)] = (+-) 2^(log2|A_ij| + r_j - n_i), n_i = ceil(max_j (log2|A_ij| + r_j)); r_j: the row
@@ -389,10 +431,12 @@ __global__ __launch_bounds__((NW + 1) * 64, 4) void affine_chunk_f64_kernel(Chai
 #pragma unroll
             for (int e = 0; e < 4; ++e) rj[e] = rsrc[p4 + 4 * e];
         }
+        const float sh = ADJ ? pre_shift : 0.0f;
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             const int row = (tid + q * NT) / LPR;
-            const float re[4] = {it[q].a[0], it[q].a[2], it[q].b[0], it[q].b[2]};
+            const float re[4] = {ADJ ? it[q].a[0] + sh : it[q].a[0], ADJ ? it[q].a[2] + sh : it[q].a[2], ADJ ? it[q].b[0] + sh : it[q].b[0],
+                                 ADJ ? it[q].b[2] + sh : it[q].b[2]};
             const float im[4] = {it[q].a[1], it[q].a[3], it[q].b[1], it[q].b[3]};
             float u = __builtin_fmaf(re[0], kHi, rj[0]);
 #pragma unroll
@@ -607,14 +651,14 @@ __global__ __launch_bounds__((NW + 1) * 64, 4) void affine_chunk_f64_kernel(Chai
     }
 }
 
-template <int DP, int NW, bool PRECISE> int launch_chunk_f64(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
+template <int DP, int NW, bool PRECISE, bool ADJ = false> int launch_chunk_f64(goom_ctx *ctx, const ChainArgs &args, long long grid, const char *label)
 {
     constexpr int LDA = DP + 4;
     const size_t lds = 2 * ((size_t)DP * LDA * sizeof(float) + (size_t)DP * sizeof(float)) + 128 + DP * sizeof(double);
     if (grid <= 0) return GOOM_OK;
     if (grid > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many chains for one launch (%lld)", grid);
     goom::prof_begin(ctx, label);
-    hipLaunchKernelGGL((affine_chunk_f64_kernel<DP, NW, PRECISE>), dim3((unsigned)grid), dim3((NW + 1) * 64), lds, ctx->stream, args);
+    hipLaunchKernelGGL((affine_chunk_f64_kernel<DP, NW, PRECISE, ADJ>), dim3((unsigned)grid), dim3((NW + 1) * 64), lds, ctx->stream, args);
     goom::prof_end(ctx);
     return goom::check_hip(ctx, hipGetLastError(), "launch affine_chunk_f64_kernel");
 }
@@ -650,13 +694,13 @@ template <typename R> __global__ __launch_bounds__(256) void replicate_power_ker
     }
 }
 
-template <int DP, bool TI> int launch_walk(goom_ctx *ctx, const ChainArgs &args, long long nchains, const char *label)
+template <int DP, bool TI, bool ADJ = false> int launch_walk(goom_ctx *ctx, const ChainArgs &args, long long nchains, const char *label)
 {
     const long long grid = (nchains + kWalkWaves - 1) / kWalkWaves;
     if (grid <= 0) return GOOM_OK;
     if (grid > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many chains for one launch (%lld)", nchains);
     goom::prof_begin(ctx, label);
-    hipLaunchKernelGGL((affine_walk_kernel<DP, TI>), dim3((unsigned)grid), dim3(kWalkWaves * 64), 0, ctx->stream, args, nchains);
+    hipLaunchKernelGGL((affine_walk_kernel<DP, TI, ADJ>), dim3((unsigned)grid), dim3(kWalkWaves * 64), 0, ctx->stream, args, nchains);
     goom::prof_end(ctx);
     return goom::check_hip(ctx, hipGetLastError(), "launch affine_walk_kernel");
 }
@@ -695,6 +739,10 @@ bool affine_walk_applies(const ChainArgs &args, int dp)
 int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long nchains, const char *label)
 {
     const bool ti = args.left_step_stride == 0;
+    if (args.left_shift) { // the adjoint recurrence: transposed factors in reverse order
+        if (ti) return goom::fail(ctx, GOOM_EUNSUPPORTED, "transposed factors in reverse order: one matrix per step");
+        return dp == 16 ? launch_walk<16, false, true>(ctx, args, nchains, label) : launch_walk<32, false, true>(ctx, args, nchains, label);
+    }
     if (dp == 16) return ti ? launch_walk<16, true>(ctx, args, nchains, label) : launch_walk<16, false>(ctx, args, nchains, label);
     return ti ? launch_walk<32, true>(ctx, args, nchains, label) : launch_walk<32, false>(ctx, args, nchains, label);
 }
@@ -705,6 +753,10 @@ int dispatch_affine_chunk_f64(goom_ctx *ctx, const ChainArgs &args, int dp, long
     if (!((dp == 16 || dp == 32) && args.n == dp && args.d == dp && args.m == dp + 1 && args.init_mode == 0 && args.out_goom == nullptr &&
           args.out_fact_steps == nullptr && args.out_fact_final != nullptr && args.fact_cols == dp + 16))
         return goom::fail(ctx, GOOM_EUNSUPPORTED, "double-state chunk products are built for d = 16 and 32");
+    if (args.left_shift) { // the adjoint recurrence: transposed factors in reverse order
+        if (args.left_step_stride == 0) return goom::fail(ctx, GOOM_EUNSUPPORTED, "transposed factors in reverse order: one matrix per step");
+        return dp == 16 ? launch_chunk_f64<16, 1, false, true>(ctx, args, grid, label) : launch_chunk_f64<32, 2, false, true>(ctx, args, grid, label);
+    }
     if (args.left_step_stride == 0) // one matrix at every step
         return dp == 16 ? launch_chunk_f64<16, 1, true>(ctx, args, grid, label) : launch_chunk_f64<32, 2, true>(ctx, args, grid, label);
     return dp == 16 ? launch_chunk_f64<16, 1, false>(ctx, args, grid, label) : launch_chunk_f64<32, 2, false>(ctx, args, grid, label);

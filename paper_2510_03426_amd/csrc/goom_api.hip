@@ -893,8 +893,12 @@ size_t goom_affine_scan_scaled_workspace_bytes(int64_t T, int d, int64_t batch, 
     return align_up(ap.total(), 256) + (affine_scaled_is_fused(ap.p, d, dtype) ? 0 : affine_states_bytes(T, d, batch, dtype));
 }
 
+// adjoint_shift: NULL, or [batch, T] floats: the recurrence then runs on the transposes of A's matrices in reverse
+// order, the log-magnitudes of step s's factor shifted by adjoint_shift[s] (the backward pass; float GOOMs with the
+// double chunk products only).
 static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H, void *scaled, void *logscale,
-                      int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes)
+                      int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes,
+                      const float *adjoint_shift = nullptr)
 {
     goom_scan_opts plain = opts ? *opts : goom_scan_opts{0, 0};
     const bool ti = (plain.flags & GOOM_AFFINE_TIME_INVARIANT) != 0;
@@ -919,6 +923,7 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
         return launch_scaled_exp(ctx, H, scaled, logscale, (size_t)batch * (size_t)T, d, dtype);
     }
     const int f64 = ap.f64 ? 1 : 0;
+    if (adjoint_shift && (!f64 || ti || want_scaled)) return fail(ctx, GOOM_EUNSUPPORTED, "transposed factors in reverse order: float GOOMs, d = 16 or 32, several chunks");
 
     ChainLaunch base;
     std::memset(&base, 0, sizeof base);
@@ -932,6 +937,7 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
     base.steps = T;
     base.bias_mode = 1;
     base.bias = bias;
+    base.left_shift = adjoint_shift;
 
     if (p.C == 1) {
         ChainLaunch l = base;
@@ -1054,6 +1060,7 @@ int goom_affine_scan_scaled(goom_ctx *ctx, const void *A, const void *bias, cons
 
 // ---- backward passes ---------------------------------------------------------------------------------------
 struct AffineBackwardPlan {
+    bool direct; // the adjoint scan reads the forward pass's matrices itself (transposed, in reverse order)
     size_t at_bytes, vec_bytes, scan_bytes;
     size_t total() const { return at_bytes + 2 * vec_bytes + scan_bytes; }
 };
@@ -1062,7 +1069,9 @@ static AffineBackwardPlan plan_affine_backward(long long T, int d, long long bat
 {
     AffineBackwardPlan p;
     const size_t cb = 2 * comp_bytes(dtype);
-    p.at_bytes = align_up((size_t)batch * (size_t)T * d * d * cb, 256);
+    p.direct = plan_affine(T, d, batch, dtype, opts).f64 && !(opts && (opts->flags & GOOM_AFFINE_TIME_INVARIANT));
+    // the transposed, reversed and rescaled copy of A, or only the shifts of its log-magnitudes, one per step
+    p.at_bytes = p.direct ? align_up((size_t)batch * (size_t)T * sizeof(float), 256) : align_up((size_t)batch * (size_t)T * d * d * cb, 256);
     p.vec_bytes = align_up((size_t)batch * (size_t)T * d * cb, 256);
     p.scan_bytes = align_up(goom_affine_scan_workspace_bytes(T, d, batch, dtype, opts), 256);
     return p;
@@ -1096,10 +1105,12 @@ int goom_affine_scan_backward(goom_ctx *ctx, const void *A, const void *bias, co
     void *mu = w + p.at_bytes + p.vec_bytes;
     void *scan_ws = w + p.at_bytes + 2 * p.vec_bytes;
     // operands of the adjoint recurrence (transposed matrices in reverse time, G / h as GOOMs) ...
-    if (int s = launch_affine_backward_prepare(ctx, A, H, grad_H, At, gt, T, d, batch, dtype)) return s;
+    if (int s = launch_affine_backward_prepare(ctx, A, H, grad_H, p.direct ? nullptr : At, p.direct ? static_cast<float *>(At) : nullptr, gt, T, d, batch, dtype)) return s;
     // ... the adjoints, by the forward scan itself ...
     ctx->prof_keep = true;
-    const int st = run_affine(ctx, At, gt, nullptr, mu, nullptr, nullptr, T, d, batch, dtype, opts, p.scan_bytes ? scan_ws : nullptr, p.scan_bytes);
+    const int st = p.direct ? run_affine(ctx, A, gt, nullptr, mu, nullptr, nullptr, T, d, batch, dtype, opts, p.scan_bytes ? scan_ws : nullptr, p.scan_bytes,
+                                         static_cast<const float *>(At))
+                            : run_affine(ctx, At, gt, nullptr, mu, nullptr, nullptr, T, d, batch, dtype, opts, p.scan_bytes ? scan_ws : nullptr, p.scan_bytes);
     ctx->prof_keep = false;
     if (st) return st;
     // ... and the gradients

@@ -160,6 +160,35 @@ template <typename R, int NW> __global__ __launch_bounds__(NW * 64) void bwd_pre
     }
 }
 
+// The same without the copy of the matrices, for the scan kernels that read A transposed and in reverse order
+// themselves: only the shift of step s's log-magnitudes, shift[b, s] = c_t - c_{t+1} (-inf for s = 0: the zero
+// matrix), and gt.  One wave per (b, s).
+template <typename R> __global__ __launch_bounds__(256) void bwd_shift_kernel(const typename C2<R>::type *__restrict__ H, const R *__restrict__ G,
+                                                                             float *__restrict__ shift, typename C2<R>::type *__restrict__ gt,
+                                                                             long long T, int d, long long nsteps)
+{
+    typedef typename C2<R>::type c2;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const long long step = (long long)blockIdx.x * 4 + wave;
+    if (step >= nsteps) return; // whole wave
+    const long long b = step / T, s = step % T;
+    const R ninf = sizeof(R) == 4 ? (R)-__builtin_huge_valf() : (R)-__builtin_huge_val();
+    const long long t = T - 1 - s;
+    const R ct = state_scale<R>(H + (size_t)(b * T + t) * d, d);
+    const R delta = s == 0 ? ninf : ct - state_scale<R>(H + (size_t)(b * T + t + 1) * d, d);
+    if (lane == 0) shift[b * T + s] = (float)delta;
+    for (int i = lane; i < d; i += 64) {
+        const R gv = G[(size_t)(b * T + t) * d + i];
+        const c2 h = H[(size_t)(b * T + t) * d + i];
+        c2 o;
+        const bool live = gv != (R)0 && h.x > ninf;
+        o.x = live ? (R)(log(__builtin_fabs((double)gv)) - ((double)h.x - (double)ct)) : ninf;
+        o.y = (live && ((gv < (R)0) != odd_phase<R>(h.y))) ? pi_of<R>() : (R)0;
+        gt[(size_t)(b * T + s) * d + i] = o;
+    }
+}
+
 // Gradients from the scaled adjoints mu[b, s] = lam[b, T - 1 - s] e^(c_{T-1-s}) (GOOMs), one wave per (b, t), no
 // workgroup barrier:
 //   gA[b, t, i, j] = lam_t[i] A_t[i, j] h_{t-1}[j],   gb[b, t, i] = lam_t[i] b_t[i].
@@ -326,10 +355,23 @@ template <typename R> static int bwd_prepare_t(goom_ctx *ctx, const void *A, con
     return bwd_prepare_launch<R, 1>(ctx, A, H, G, At, gt, T, d, batch);
 }
 
-int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d,
+template <typename R> static int bwd_shift_t(goom_ctx *ctx, const void *H, const void *G, float *shift, void *gt, long long T, int d, long long batch)
+{
+    typedef typename C2<R>::type c2;
+    const long long nsteps = batch * T;
+    prof_begin(ctx, "affine_backward_prepare_operands");
+    hipLaunchKernelGGL(bwd_shift_kernel<R>, dim3((unsigned)((nsteps + 3) / 4)), dim3(256), 0, ctx->stream, static_cast<const c2 *>(H),
+                       static_cast<const R *>(G), shift, static_cast<c2 *>(gt), T, d, nsteps);
+    prof_end(ctx);
+    return check_hip(ctx, hipGetLastError(), "launch bwd_shift_kernel");
+}
+
+// At: the transposed, reversed, rescaled copy of A; or NULL, and then shift receives the shifts alone
+int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, float *shift, void *gt, long long T, int d,
                                    long long batch, int dtype)
 {
     if (batch * T > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
+    if (!At) return dtype == GOOM_C64 ? bwd_shift_t<float>(ctx, H, G, shift, gt, T, d, batch) : bwd_shift_t<double>(ctx, H, G, shift, gt, T, d, batch);
     return dtype == GOOM_C64 ? bwd_prepare_t<float>(ctx, A, H, G, At, gt, T, d, batch) : bwd_prepare_t<double>(ctx, A, H, G, At, gt, T, d, batch);
 }
 

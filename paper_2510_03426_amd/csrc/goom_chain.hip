@@ -75,6 +75,9 @@ int launch_chain(goom_ctx *ctx, const ChainLaunch &l)
     a.out_logscale = static_cast<float *>(l.out_logscale);
     a.fact_f64 = l.fact_f64;
     a.acc_f64 = l.acc_f64;
+    a.left_shift = l.left_shift;
+    if (l.left_shift && !(l.dtype == GOOM_C64 && !l.left_fact && !l.left_real && !l.io_c64 && (l.acc_f64 || (l.m == 1 && l.fact_f64)) && l.left_step_stride > 0))
+        return fail(ctx, GOOM_EUNSUPPORTED, "transposed factors in reverse order: double chunk products and the walk beside them only");
     if ((l.fact_f64 || l.acc_f64) && (l.dtype != GOOM_C64 || l.left_fact))
         return fail(ctx, GOOM_EUNSUPPORTED, "double factored matrices beside float GOOMs: recurrence kernels only");
     if (a.out_scaled && (l.dtype != GOOM_C64 || l.left_fact))

@@ -61,6 +61,10 @@ struct ChainArgs {
     // float kernels of the recurrence working beside double chunk products and carries:
     int fact_f64;        // 1: the factored matrices read (init_mode 1) and written (out_fact_final) have double mantissas
     int acc_f64;         // 1: chunk products [A* | b*] with the running product in double (d = 16, 32)
+    // adjoint recurrence (backward pass of the recurrence), the double chunk products and the matrix-vector walk only:
+    // NULL, or [batch, steps] floats; the factor of step s is then the transpose of matrix steps - s of the array
+    // `left` (any matrix for s = 0) with left_shift[s] added to every log-magnitude (-inf: a zero matrix)
+    const float *left_shift;
 };
 
 template <typename R> struct Comp;

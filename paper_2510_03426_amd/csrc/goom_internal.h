@@ -97,6 +97,7 @@ struct ChainLaunch {
                           // product and every factored matrix are double
     int fact_f64;         // float kernels of the recurrence: factored matrices read / written have double mantissas
     int acc_f64;          // chunk products of the recurrence with the running product in double (float GOOM factors)
+    const float *left_shift; // NULL, or [batch, steps]: factors read transposed in reverse order, log-magnitudes shifted (see ChainArgs)
     const char *label;    // phase name for profiling records
 };
 int launch_chain(goom_ctx *ctx, const ChainLaunch &a);
@@ -161,7 +162,7 @@ int launch_matrix_probe(goom_ctx *ctx, void *sink, long long iters, int dtype);
 // backward passes (goom_backward.hip)
 int launch_to_goom_backward(goom_ctx *ctx, const void *x, const void *g, void *gx, size_t n, int dtype, double eps);
 int launch_from_goom_backward(goom_ctx *ctx, const void *y, const void *gx, void *g, size_t n, int dtype, double eps);
-int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d,
+int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, float *shift, void *gt, long long T, int d,
                                    long long batch, int dtype);
 int launch_affine_backward_gradients(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
                                      void *gb, void *gh0, long long T, int d, long long batch, int dtype);

@@ -827,7 +827,8 @@ def test_codec_backward_redefined_derivatives(G, oracle, comp):
 @pytest.mark.parametrize("T,d,batch,chunk,ctype,with_h0,gain", [
     (300, 32, 2, 32, np.complex64, False, 1.05), (1000, 16, 2, 0, np.complex64, True, 1.05), (4000, 32, 1, 0, np.complex64, True, 1.3),
     (64, 8, 3, 9, np.complex64, True, 1.05), (257, 64, 1, 40, np.complex64, False, 1.05), (200, 16, 2, 16, np.complex128, True, 1.05),
-    (1, 32, 2, 0, np.complex64, True, 1.05), (40, 128, 1, 8, np.complex128, True, 1.05), (50, 31, 2, 0, np.complex64, False, 1.05)])
+    (1, 32, 2, 0, np.complex64, True, 1.05), (40, 128, 1, 8, np.complex128, True, 1.05), (50, 31, 2, 0, np.complex64, False, 1.05),
+    (601, 16, 2, 50, np.complex64, False, 1.05)])
 def test_affine_scan_backward(G, oracle, T, d, batch, chunk, ctype, with_h0, gain):
     """Gradients of L = sum grad_h * Re h with respect to the log-magnitudes of A, bias and h0, against the oracle's
     adjoint recurrence fed the same forward states."""
