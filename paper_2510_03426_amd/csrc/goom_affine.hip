@@ -186,7 +186,7 @@ template <int DP, bool TI, bool ADJ = false> __global__ __launch_bounds__(kWalkW
                     v = __builtin_amdgcn_exp2f(t); // 2^-inf = 0 covers zero entries and zero rows
                 }
                 const float kf = __builtin_fmaf(im[e], 0.318309886183790671538f, 12582912.0f);
-                sv[q][e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) ^ (__builtin_bit_cast(int, kf) << 31));
+                sv[q][e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) | (__builtin_bit_cast(int, kf) << 31));
             }
         }
     };
@@ -460,7 +460,7 @@ __global__ __launch_bounds__((NW + 1) * 64, 4) void affine_chunk_f64_kernel(Chai
                     v = __builtin_amdgcn_exp2f(t);
                 }
                 const float kf = __builtin_fmaf(im[e], 0.318309886183790671538f, 12582912.0f);
-                tile[row * LDA + p4 + 4 * e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) ^ (__builtin_bit_cast(int, kf) << 31));
+                tile[row * LDA + p4 + 4 * e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) | (__builtin_bit_cast(int, kf) << 31));
             }
             nsh[CD::phys(row)] = n; // every lane of the row writes the same value
         }

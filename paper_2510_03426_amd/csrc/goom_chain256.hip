@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kThreads256, kSlabs == 1 ? 2 : 1) void chain256_ker
                 t = __builtin_fmaf(pre[q][e].x, kLo, t);
                 const float v = __builtin_amdgcn_exp2f(t); // 2^-inf = 0 covers zero entries and the padding
                 const float kf = __builtin_fmaf(pre[q][e].y, 0.318309886183790671538f, 12582912.0f);
-                y[e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) ^ (__builtin_bit_cast(int, kf) << 31));
+                y[e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) | (__builtin_bit_cast(int, kf) << 31));
             }
             *reinterpret_cast<f4 *>(&tile[row * kLDA + c4]) = y;
             if (first_block && c4 == 0) nsh_all[parity * kDP + row] = npre[q];

@@ -192,9 +192,10 @@ __device__ __forceinline__ void chain_body(const ChainArgs &a)
                 float t = __builtin_fmaf(re[e], kHi, rj[e] - nsub);
                 t = __builtin_fmaf(re[e], kLo, t);
                 const float v = __builtin_amdgcn_exp2f(t); // 2^-inf = 0 covers zero entries
-                // parity of round(im / pi), read off the last mantissa bit after adding 1.5 * 2^23
+                // parity of round(im / pi), read off the last mantissa bit after adding 1.5 * 2^23, and put on the sign
+                // bit with one shift-and-or (v is an exponential: its own sign bit is clear)
                 const float kf = __builtin_fmaf(im[e], 0.318309886183790671538f, 12582912.0f);
-                y[e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) ^ (__builtin_bit_cast(int, kf) << 31));
+                y[e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) | (__builtin_bit_cast(int, kf) << 31));
             }
             *reinterpret_cast<f4 *>(&tile[row * LDA + c4]) = y;
             nsh[row] = n; // every lane of the row writes the same value

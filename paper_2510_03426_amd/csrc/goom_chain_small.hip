@@ -156,7 +156,7 @@ template <int D, bool OUT> __global__ __launch_bounds__(64, 6) void small_chain_
             tt = __builtin_fmaf(re[e], kLo, tt);
             const float v = __builtin_amdgcn_exp2f(tt);
             const float kf = __builtin_fmaf(im[e], 0.318309886183790671538f, 12582912.0f);
-            y[e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) ^ (__builtin_bit_cast(int, kf) << 31));
+            y[e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) | (__builtin_bit_cast(int, kf) << 31));
         }
         *reinterpret_cast<f4 *>(&tile[crow * kSmallLDA + c4]) = y;
         nsh[crow] = n;
