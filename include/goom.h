@@ -244,7 +244,7 @@ typedef struct goom_reset_opts {
  * prefix states at chunk boundaries: a selected state is replaced by the orthonormal
  * factor Q of its column-normalised real form (paper Section 4.2.1 (a)), and all later
  * states continue from Q.
- * Both formats, d <= 64.  Chunk products, the prefixes at the chunk boundaries and the
+ * Both formats, d <= 128 (goom_lyapunov_spectrum as well).  Chunk products, the prefixes at the chunk boundaries and the
  * factorisations are computed in double for both formats; complex64 states are rounded once,
  * when they are stored.
  * J: [batch, T, d, d]; S0: NULL or [batch, d, d]; states: [batch, T, d, d] (the state

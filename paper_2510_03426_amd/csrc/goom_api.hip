@@ -470,7 +470,7 @@ static int run_reset(goom_ctx *ctx, const void *J, const void *S0, void *states,
     if (int s = check_common(ctx, dtype)) return s;
     if (!J) return fail(ctx, GOOM_EINVAL, "null data pointer");
     if (T <= 0 || batch <= 0 || d <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive (T=%lld d=%d batch=%lld)", T, d, batch);
-    if (d > 64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 64 (d=%d)", d);
+    if (d > GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= %d (d=%d)", GOOM_MAX_DIM, d);
     if (opts && opts->chunk_len < 0) return fail(ctx, GOOM_EINVAL, "negative chunk_len");
     const int policy = opts ? opts->policy : GOOM_RESET_ALWAYS;
     if (policy < GOOM_RESET_NEVER || policy > GOOM_RESET_ALWAYS) return fail(ctx, GOOM_EINVAL, "unknown reset policy %d", policy);
@@ -1143,7 +1143,7 @@ int goom_from_goom_backward(goom_ctx *ctx, const void *y, const void *grad_x, vo
 
 size_t goom_scan_reset_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts)
 {
-    if (T <= 0 || d <= 0 || batch <= 0 || d > 64 || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
+    if (T <= 0 || d <= 0 || batch <= 0 || d > GOOM_MAX_DIM || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
     const ResetPlan p = plan_reset(T, d, batch, dtype, opts);
     return p.total();
 }

@@ -264,7 +264,7 @@ __device__ inline double rsqrt_d(double x)
 }
 
 // elimination of one panel (see eliminate_panel above), columns in double
-template <int DP> __device__ void eliminate_panel_d(d4 &G, d4 (&Zp)[DP / 16], double &piv, WaveD<DP> &s, int g, int c)
+template <int DP, typename S> __device__ void eliminate_panel_d(d4 &G, d4 (&Zp)[DP / 16], double &piv, S &s, int g, int c)
 {
     constexpr int KT = DP / 16;
 #pragma unroll
@@ -646,6 +646,352 @@ template <int DP, typename IO> __global__ __launch_bounds__(64) void reset_carry
 #pragma unroll
             for (int nt = 0; nt < KT; ++nt)
                 if (16 * nt + c < d) a.growth[b * d + 16 * nt + c] = 0.5 * (log(pprod[nt]) + pexp[nt] * kLn2) * a.growth_scale;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// The carry kernel for 64 < d <= 128.  A state of 128 x 128 doubles is more than one wave's registers hold, so a
+// workgroup of four waves owns a batch item, wave w the columns 32 w .. 32 w + 31 of the state (two panels of
+// sixteen).  Z = T_c Y is formed slab by slab from one LDS tile of the chunk product; the factorisation then
+// walks the eight panels in order: the wave that owns a panel makes it orthogonal to the finished ones (which
+// lie in LDS, in the tile's place), factorises it as above and lays it down for the others.  Arithmetic, layouts
+// and bookkeeping are those of the one-wave kernel.
+struct WideScratch {
+    double rrow[2][16];
+    double rperm[2][16];
+    double qcol[2][128];
+    double diag[128];
+    double red[4];
+    int hit;
+};
+
+template <typename IO> __global__ __launch_bounds__(256) void reset_carry_wide_kernel(ResetArgs a)
+{
+    constexpr int DP = 128, KT = DP / 16, NL = 2, NW = 4, LDT = DP + 2, LDQ = 18;
+    constexpr int TQ = DP * DP / 4 / (NW * 64); // 32-byte pieces of the chunk product per thread
+    extern __shared__ __align__(32) unsigned char smem[];
+    double *tile = reinterpret_cast<double *>(smem); // [128][130]: chunk product, columns in perm16 order
+    auto panel = [&](int q) { return reinterpret_cast<double *>(smem) + (size_t)q * DP * LDQ; }; // [8][128][18], after the product
+    WideScratch &s = *reinterpret_cast<WideScratch *>(smem + (size_t)KT * DP * LDQ * sizeof(double));
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+    const int pc = ((c & 3) << 2) | (c >> 2); // position of column c inside a stored panel
+    const int d = a.d;
+    const long long b = blockIdx.x;
+    const size_t tot_mant = (size_t)DP * a.tot_cols * sizeof(double);
+    const size_t car_mant = (size_t)DP * a.car_cols * sizeof(double);
+
+    d4 Y[NL][KT]; // Y[nl][mt][v] = entry (row 16 mt + 4 v + g, column 32 wave + 16 nl + c), columns scaled by 2^yexp
+    double yexp[NL], pprod[NL], pexp[NL];
+#pragma unroll
+    for (int nl = 0; nl < NL; ++nl) {
+        yexp[nl] = 0.0;
+        pprod[nl] = 1.0;
+        pexp[nl] = 0.0;
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Y[nl][mt][v] = (16 * mt + 4 * v + g == 32 * wave + 16 * nl + c) ? 1.0 : 0.0;
+    }
+    if (a.s0) {
+        const IO *gp = reinterpret_cast<const IO *>(a.s0) + (size_t)b * d * d * 2;
+#pragma unroll
+        for (int nl = 0; nl < NL; ++nl) {
+            const int col = 32 * wave + 16 * nl + c;
+            if (col < d) {
+                double cmax = -__builtin_huge_val();
+                for (int i = 0; i < d; ++i) cmax = fmax(cmax, (double)gp[((size_t)i * d + col) * 2]);
+                yexp[nl] = cmax > -__builtin_huge_val() ? ceil(cmax * kLog2e) : 0.0;
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = 16 * mt + 4 * v + g;
+                        double val = 0.0;
+                        if (row < d) {
+                            const IO *e = gp + ((size_t)row * d + col) * 2;
+                            const double t = (double)e[0] * kLog2e - yexp[nl];
+                            val = t > -1000.0 ? exp2(t) : 0.0;
+                            if ((int)rint((double)e[1] * 0.318309886183790671538) & 1) val = -val;
+                        }
+                        Y[nl][mt][v] = val;
+                    }
+            }
+        }
+    }
+
+    auto store_carry = [&](long long cc) {
+        unsigned char *dst = a.carries + (b * (a.C + 1) + cc) * a.car_stride;
+        double *mp = reinterpret_cast<double *>(dst);
+        double *ep = reinterpret_cast<double *>(dst + car_mant);
+#pragma unroll
+        for (int nl = 0; nl < NL; ++nl) {
+            const int col = 32 * wave + 16 * nl + c;
+            if (col < a.car_cols) {
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = 16 * mt + 4 * v + g;
+                        mp[(size_t)row * a.car_cols + col] = (row < d && col < d) ? Y[nl][mt][v] : 0.0;
+                    }
+                if (g == 0) ep[col] = col < d ? yexp[nl] : 0.0;
+            }
+        }
+    };
+
+    // one factorisation of Z in place (Z <- Q): see qr_panels_d; piv, cexp for this wave's two panels; returns the
+    // largest (squared column norm) / pivot over the whole matrix
+    auto qr_pass = [&](d4 (&Z)[NL][KT], double (&piv)[NL], double (&cexp)[NL]) {
+        double norm2[NL];
+#pragma unroll
+        for (int nl = 0; nl < NL; ++nl) {
+            double mx = 0.0;
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) mx = fmax(mx, fabs(Z[nl][mt][v]));
+            mx = fmax(mx, __shfl_xor(mx, 16, 64));
+            mx = fmax(mx, __shfl_xor(mx, 32, 64));
+            int ex = 0;
+            if (mx > 0.0) (void)frexp(mx, &ex);
+            cexp[nl] = (double)ex;
+            double sum = 0.0;
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    Z[nl][mt][v] = ldexp(Z[nl][mt][v], -ex);
+                    sum = fma(Z[nl][mt][v], Z[nl][mt][v], sum);
+                }
+            sum += __shfl_xor(sum, 16, 64);
+            sum += __shfl_xor(sum, 32, 64);
+            norm2[nl] = sum;
+            piv[nl] = 1.0;
+        }
+        __syncthreads(); // (whoever still read the LDS panels or the tile is done)
+        // one panel: orthogonal to the finished ones, twice (see qr_panels_d), then factorised and laid down
+        auto finish_panel = [&](int P, d4 (&Zp)[KT], double &pv) {
+#pragma unroll 1
+            for (int rep = 0; rep < 2; ++rep)
+#pragma unroll 1
+                for (int q = 0; q < P; ++q) {
+                    const double *pq = panel(q);
+                    d4 R = {0., 0., 0., 0.};
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) R = mfma8(pq[(16 * kt + 4 * v + g) * LDQ + pc], Zp[kt][v], R);
+                    R = -R;
+#pragma unroll
+                    for (int mt = 0; mt < KT; ++mt) {
+                        const d4 av = *reinterpret_cast<const d4 *>(&pq[(16 * mt + c) * LDQ + 4 * g]);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) Zp[mt] = mfma8(av[v], R[v], Zp[mt]);
+                    }
+                }
+            d4 G = {0., 0., 0., 0.};
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) G = mfma8(Zp[kt][v], Zp[kt][v], G);
+            eliminate_panel_d<DP>(G, Zp, pv, s, g, c);
+            const double sc = pv > 1.0e-280 ? rsqrt_d(pv) : 0.0;
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) Zp[mt] *= sc;
+            if (P + 1 < KT) {
+                double *pp = panel(P);
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) pp[(16 * mt + 4 * v + g) * LDQ + pc] = Zp[mt][v];
+            }
+        };
+#pragma unroll 1
+        for (int P = 0; P < KT; ++P) {
+            if (wave == P / NL) {
+                if (P % NL == 0)
+                    finish_panel(P, Z[0], piv[0]);
+                else
+                    finish_panel(P, Z[1], piv[1]);
+            }
+            __syncthreads();
+        }
+        double worst = 1.0;
+#pragma unroll
+        for (int nl = 0; nl < NL; ++nl) {
+            const double ratio = piv[nl] > 1.0e-280 ? norm2[nl] * rcp_d(piv[nl]) : 1.0;
+            worst = fmax(worst, ratio);
+        }
+#pragma unroll
+        for (int sft = 1; sft < 16; sft <<= 1) worst = fmax(worst, __shfl_xor(worst, sft, 64));
+        if (lane == 0) s.red[wave] = worst;
+        __syncthreads();
+        worst = fmax(fmax(s.red[0], s.red[1]), fmax(s.red[2], s.red[3]));
+        __syncthreads();
+        return worst;
+    };
+    auto qr_in_place = [&](d4 (&Z)[NL][KT], const double (&colexp)[NL]) {
+        double piv[NL], piv2[NL], ce[NL], ce2[NL];
+        const double amp = qr_pass(Z, piv, ce);
+#pragma unroll
+        for (int nl = 0; nl < NL; ++nl) {
+            piv2[nl] = 1.0;
+            ce2[nl] = 0.0;
+        }
+        if (amp > (sizeof(IO) == 4 ? 1.0e10 : 1.0e3)) (void)qr_pass(Z, piv2, ce2); // (the same in every wave)
+#pragma unroll
+        for (int nl = 0; nl < NL; ++nl)
+            if (piv[nl] > 1.0e-280 && piv2[nl] > 1.0e-280) {
+                int e;
+                pprod[nl] = frexp(pprod[nl] * piv[nl] * piv2[nl], &e);
+                pexp[nl] += 2.0 * (colexp[nl] + ce[nl] + ce2[nl]) + (double)e;
+            }
+    };
+
+    for (long long cc = 0; cc < a.C; ++cc) {
+        store_carry(cc);
+        const unsigned char *tp = a.totals + (b * a.C + cc) * a.tot_stride;
+        const double tex = *reinterpret_cast<const double *>(tp + tot_mant);
+        __syncthreads(); // (the panels of the chunk before are done with)
+#pragma unroll 4
+        for (int q = 0; q < TQ; ++q) {
+            const int piece = tid + NW * 64 * q;
+            const int row = piece / (DP / 4), c4 = 4 * (piece % (DP / 4));
+            const int p4 = (c4 & ~15) | ((c4 >> 2) & 3);
+            d4 val = {0., 0., 0., 0.};
+            if (c4 < a.tot_cols) val = *reinterpret_cast<const d4 *>(reinterpret_cast<const double *>(tp) + (size_t)row * a.tot_cols + c4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                double x = val[e];
+                if (row >= d || c4 + e >= d) x = (c4 + e == row) ? 1.0 : 0.0; // identity block past d
+                tile[row * LDT + p4 + 4 * e] = x;
+            }
+        }
+        __syncthreads();
+        // ---- Z = T_c Y
+        d4 Z[NL][KT];
+#pragma unroll
+        for (int nl = 0; nl < NL; ++nl)
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) Z[nl][mt] = d4{0., 0., 0., 0.};
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                const d4 av = *reinterpret_cast<const d4 *>(&tile[(16 * mt + c) * LDT + 16 * kt + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int nl = 0; nl < NL; ++nl) Z[nl][mt] = mfma8(av[v], Y[nl][kt][v], Z[nl][mt]);
+            }
+        double zexp[NL];
+#pragma unroll
+        for (int nl = 0; nl < NL; ++nl) zexp[nl] = yexp[nl] + tex;
+
+        const long long t_end = (cc + 1) * a.L;
+        const bool boundary = t_end <= a.T && a.policy >= 0;
+        bool did_reset = false;
+        if (boundary) {
+            did_reset = a.policy == 1;
+            if (!did_reset) {
+                // squared cosines between columns: Z goes to LDS panel by panel, every wave takes the pairs whose
+                // second column is its own
+                __syncthreads(); // the tile is free
+#pragma unroll
+                for (int nl = 0; nl < NL; ++nl) {
+                    double *pp = panel(NL * wave + nl);
+#pragma unroll
+                    for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) pp[(16 * mt + 4 * v + g) * LDQ + pc] = Z[nl][mt][v];
+                    d4 Gd = {0., 0., 0., 0.};
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) Gd = mfma8(Z[nl][kt][v], Z[nl][kt][v], Gd);
+                    double dsel = Gd[0];
+                    dsel = (c >> 2) == 1 ? Gd[1] : dsel;
+                    dsel = (c >> 2) == 2 ? Gd[2] : dsel;
+                    dsel = (c >> 2) == 3 ? Gd[3] : dsel;
+                    if (g == (c & 3)) s.diag[32 * wave + 16 * nl + c] = dsel;
+                }
+                if (tid == 0) s.hit = 0;
+                __syncthreads();
+                bool hit = false;
+                const double thr2 = (double)a.cos_threshold * (double)a.cos_threshold;
+#pragma unroll
+                for (int nl = 0; nl < NL; ++nl) {
+                    const int P = NL * wave + nl;
+                    const double dc = s.diag[16 * P + c];
+                    for (int q = 0; q <= P; ++q) {
+                        const double *pq = panel(q);
+                        d4 Gt = {0., 0., 0., 0.}; // rows: columns 16 q + .. of Z, columns: 16 P + c
+#pragma unroll
+                        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) Gt = mfma8(pq[(16 * kt + 4 * v + g) * LDQ + pc], Z[nl][kt][v], Gt);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int row = 16 * q + 4 * v + g, col = 16 * P + c;
+                            const double dr = s.diag[row];
+                            const double x = Gt[v];
+                            if (row < col && col < d && x * x > thr2 * dr * dc) hit = true;
+                        }
+                    }
+                }
+                if (__builtin_amdgcn_ballot_w64(hit) != 0 && lane == 0) s.hit = 1;
+                __syncthreads();
+                did_reset = s.hit != 0;
+            }
+        }
+        if (did_reset) {
+            qr_in_place(Z, zexp);
+#pragma unroll
+            for (int nl = 0; nl < NL; ++nl) {
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt) Y[nl][mt] = Z[nl][mt];
+                yexp[nl] = 0.0;
+            }
+        } else {
+#pragma unroll
+            for (int nl = 0; nl < NL; ++nl) {
+                double mx = 0.0;
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) mx = fmax(mx, fabs(Z[nl][mt][v]));
+                mx = fmax(mx, __shfl_xor(mx, 16, 64));
+                mx = fmax(mx, __shfl_xor(mx, 32, 64));
+                int ex = 0;
+                if (mx > 0.0) (void)frexp(mx, &ex);
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) Y[nl][mt][v] = ldexp(Z[nl][mt][v], -ex);
+                yexp[nl] = zexp[nl] + (double)ex;
+            }
+        }
+        if (tid == 0) a.chunk_flags[b * a.C + cc] = did_reset ? 1 : 0;
+    }
+
+    store_carry(a.C); // the final state
+
+    if (a.growth) { // growth of the final state (factorised, not replaced)
+        d4 Z[NL][KT];
+#pragma unroll
+        for (int nl = 0; nl < NL; ++nl)
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) Z[nl][mt] = Y[nl][mt];
+        qr_in_place(Z, yexp);
+        if (g == 0) {
+#pragma unroll
+            for (int nl = 0; nl < NL; ++nl) {
+                const int col = 32 * wave + 16 * nl + c;
+                if (col < d) a.growth[b * d + col] = 0.5 * (log(pprod[nl]) + pexp[nl] * kLn2) * a.growth_scale;
+            }
         }
     }
 }
@@ -1379,7 +1725,19 @@ int launch_reset_carry(goom_ctx *ctx, const ResetLaunch &l)
     a.policy = l.policy;
     a.cos_threshold = l.cos_threshold;
     const int dp = padded_dim(l.d);
-    if (dp != 16 && dp != 32 && dp != 64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 64 (d=%d)", l.d);
+    if (l.d > 128) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 128 (d=%d)", l.d);
+    if (dp == 128) { // four waves per batch item, the state's columns divided among them
+        const size_t lds = (size_t)8 * 128 * 18 * sizeof(double) + sizeof(WideScratch);
+        const void *kern = l.dtype == GOOM_C64 ? reinterpret_cast<const void *>(reset_carry_wide_kernel<float>) : reinterpret_cast<const void *>(reset_carry_wide_kernel<double>);
+        if (int st = check_hip(ctx, hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "hipFuncSetAttribute(reset_carry_wide_kernel)")) return st;
+        prof_begin(ctx, "reset_phase2_carries_qr");
+        if (l.dtype == GOOM_C64)
+            hipLaunchKernelGGL(reset_carry_wide_kernel<float>, dim3((unsigned)l.batch), dim3(256), lds, ctx->stream, a);
+        else
+            hipLaunchKernelGGL(reset_carry_wide_kernel<double>, dim3((unsigned)l.batch), dim3(256), lds, ctx->stream, a);
+        prof_end(ctx);
+        return check_hip(ctx, hipGetLastError(), "launch reset_carry_wide_kernel");
+    }
     prof_begin(ctx, "reset_phase2_carries_qr");
 #define GOOM_RESET_CASE(DPV)                                                                                                   \
     if (dp == DPV) {                                                                                                           \
