@@ -289,7 +289,7 @@ int goom_lyapunov_spectrum(goom_ctx *ctx, const void *J, const void *S0, void *s
  * (d) S*_t -> R_t, and lambda[b, k] = mean over t of log R_t,kk / dt.  Every step of (b)-(d)
  * is independent of the others.  states: NULL or [batch, T, d, d] (as in goom_scan_reset);
  * step_logs: NULL or [batch, T, d] doubles receiving log R_t,kk; lambda: [batch, d] doubles.
- * Both formats (complex128: factorisations and products in double), d <= 64.
+ * Both formats (complex128, and both formats above d = 64: factorisations and products in double), d <= 128.
  * workspace: goom_lyapunov_spectrum_per_step_workspace_bytes(..., states != NULL,
  * step_logs != NULL) bytes. */
 int goom_lyapunov_spectrum_per_step(goom_ctx *ctx, const void *J, const void *S0, void *states,

@@ -1221,7 +1221,7 @@ int goom_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, 
 size_t goom_lyapunov_spectrum_per_step_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts,
                                                        int caller_has_states, int caller_has_step_logs)
 {
-    if (T <= 0 || d <= 0 || batch <= 0 || d > 64 || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
+    if (T <= 0 || d <= 0 || batch <= 0 || d > GOOM_MAX_DIM || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
     const ResetPlan p = plan_reset(T, d, batch, dtype, opts);
     size_t n = p.total() + lyap_steps_partial_bytes(batch, d);
     if (!caller_has_states) n += align_up((size_t)batch * T * d * d * 2 * comp_bytes(dtype), 256);
@@ -1237,7 +1237,7 @@ int goom_lyapunov_spectrum_per_step(goom_ctx *ctx, const void *J, const void *S0
     if (!lambda || !J) return fail(ctx, GOOM_EINVAL, "null data pointer");
     if (!(dt > 0.0)) return fail(ctx, GOOM_EINVAL, "dt must be positive");
     if (T <= 0 || batch <= 0 || d <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive (T=%lld d=%d batch=%lld)", (long long)T, d, (long long)batch);
-    if (d > 64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 64 (d=%d)", d);
+    if (d > GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= %d (d=%d)", GOOM_MAX_DIM, d);
     if (step_logs && !aligned(step_logs, 8)) return fail(ctx, GOOM_EINVAL, "step_logs must be 8-byte aligned");
     const size_t need = goom_lyapunov_spectrum_per_step_workspace_bytes(T, d, batch, dtype, opts, states != nullptr, step_logs != nullptr);
     if (int s = check_workspace(ctx, workspace, workspace_bytes, need)) return s;

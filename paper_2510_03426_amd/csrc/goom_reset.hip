@@ -666,6 +666,105 @@ struct WideScratch {
     int hit;
 };
 
+// One factorisation of a 128 x 128 matrix held by four waves (wave w: columns 32 w .. 32 w + 31 as two panels) in
+// place, Z <- Q: see qr_panels_d.  piv, cexp: pivots and column exponents of this wave's two panels.  Returns the
+// largest (squared column norm) / pivot over the whole matrix, the same in every wave.  Finished panels lie in
+// LDS at `panels` ([8][128][18] doubles); all four waves must call this together.
+__device__ double wide_qr_pass(d4 (&Z)[2][8], double (&piv)[2], double (&cexp)[2], double *panels, WideScratch &s, int wave, int lane)
+{
+    constexpr int DP = 128, KT = 8, NL = 2, LDQ = 18;
+    const int g = lane >> 4, c = lane & 15;
+    const int pc = ((c & 3) << 2) | (c >> 2);
+    auto panel = [&](int q) { return panels + (size_t)q * DP * LDQ; };
+    double norm2[NL];
+#pragma unroll
+    for (int nl = 0; nl < NL; ++nl) {
+        double mx = 0.0;
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) mx = fmax(mx, fabs(Z[nl][mt][v]));
+        mx = fmax(mx, __shfl_xor(mx, 16, 64));
+        mx = fmax(mx, __shfl_xor(mx, 32, 64));
+        int ex = 0;
+        if (mx > 0.0) (void)frexp(mx, &ex);
+        cexp[nl] = (double)ex;
+        double sum = 0.0;
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                Z[nl][mt][v] = ldexp(Z[nl][mt][v], -ex);
+                sum = fma(Z[nl][mt][v], Z[nl][mt][v], sum);
+            }
+        sum += __shfl_xor(sum, 16, 64);
+        sum += __shfl_xor(sum, 32, 64);
+        norm2[nl] = sum;
+        piv[nl] = 1.0;
+    }
+    __syncthreads(); // (whoever still read the LDS panels or the tile is done)
+    // one panel: orthogonal to the finished ones, twice (see qr_panels_d), then factorised and laid down
+    auto finish_panel = [&](int P, d4 (&Zp)[KT], double &pv) {
+#pragma unroll 1
+        for (int rep = 0; rep < 2; ++rep)
+#pragma unroll 1
+            for (int q = 0; q < P; ++q) {
+                const double *pq = panel(q);
+                d4 R = {0., 0., 0., 0.};
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) R = mfma8(pq[(16 * kt + 4 * v + g) * LDQ + pc], Zp[kt][v], R);
+                R = -R;
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt) {
+                    const d4 av = *reinterpret_cast<const d4 *>(&pq[(16 * mt + c) * LDQ + 4 * g]);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) Zp[mt] = mfma8(av[v], R[v], Zp[mt]);
+                }
+            }
+        d4 G = {0., 0., 0., 0.};
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) G = mfma8(Zp[kt][v], Zp[kt][v], G);
+        eliminate_panel_d<DP>(G, Zp, pv, s, g, c);
+        const double sc = pv > 1.0e-280 ? rsqrt_d(pv) : 0.0;
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) Zp[mt] *= sc;
+        if (P + 1 < KT) {
+            double *pp = panel(P);
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) pp[(16 * mt + 4 * v + g) * LDQ + pc] = Zp[mt][v];
+        }
+    };
+#pragma unroll 1
+    for (int P = 0; P < KT; ++P) {
+        if (wave == P / NL) {
+            if (P % NL == 0)
+                finish_panel(P, Z[0], piv[0]);
+            else
+                finish_panel(P, Z[1], piv[1]);
+        }
+        __syncthreads();
+    }
+    double worst = 1.0;
+#pragma unroll
+    for (int nl = 0; nl < NL; ++nl) {
+        const double ratio = piv[nl] > 1.0e-280 ? norm2[nl] * rcp_d(piv[nl]) : 1.0;
+        worst = fmax(worst, ratio);
+    }
+#pragma unroll
+    for (int sft = 1; sft < 16; sft <<= 1) worst = fmax(worst, __shfl_xor(worst, sft, 64));
+    if (lane == 0) s.red[wave] = worst;
+    __syncthreads();
+    worst = fmax(fmax(s.red[0], s.red[1]), fmax(s.red[2], s.red[3]));
+    __syncthreads();
+    return worst;
+}
+
 template <typename IO> __global__ __launch_bounds__(256) void reset_carry_wide_kernel(ResetArgs a)
 {
     constexpr int DP = 128, KT = DP / 16, NL = 2, NW = 4, LDT = DP + 2, LDQ = 18;
@@ -742,97 +841,7 @@ template <typename IO> __global__ __launch_bounds__(256) void reset_carry_wide_k
         }
     };
 
-    // one factorisation of Z in place (Z <- Q): see qr_panels_d; piv, cexp for this wave's two panels; returns the
-    // largest (squared column norm) / pivot over the whole matrix
-    auto qr_pass = [&](d4 (&Z)[NL][KT], double (&piv)[NL], double (&cexp)[NL]) {
-        double norm2[NL];
-#pragma unroll
-        for (int nl = 0; nl < NL; ++nl) {
-            double mx = 0.0;
-#pragma unroll
-            for (int mt = 0; mt < KT; ++mt)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) mx = fmax(mx, fabs(Z[nl][mt][v]));
-            mx = fmax(mx, __shfl_xor(mx, 16, 64));
-            mx = fmax(mx, __shfl_xor(mx, 32, 64));
-            int ex = 0;
-            if (mx > 0.0) (void)frexp(mx, &ex);
-            cexp[nl] = (double)ex;
-            double sum = 0.0;
-#pragma unroll
-            for (int mt = 0; mt < KT; ++mt)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    Z[nl][mt][v] = ldexp(Z[nl][mt][v], -ex);
-                    sum = fma(Z[nl][mt][v], Z[nl][mt][v], sum);
-                }
-            sum += __shfl_xor(sum, 16, 64);
-            sum += __shfl_xor(sum, 32, 64);
-            norm2[nl] = sum;
-            piv[nl] = 1.0;
-        }
-        __syncthreads(); // (whoever still read the LDS panels or the tile is done)
-        // one panel: orthogonal to the finished ones, twice (see qr_panels_d), then factorised and laid down
-        auto finish_panel = [&](int P, d4 (&Zp)[KT], double &pv) {
-#pragma unroll 1
-            for (int rep = 0; rep < 2; ++rep)
-#pragma unroll 1
-                for (int q = 0; q < P; ++q) {
-                    const double *pq = panel(q);
-                    d4 R = {0., 0., 0., 0.};
-#pragma unroll
-                    for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) R = mfma8(pq[(16 * kt + 4 * v + g) * LDQ + pc], Zp[kt][v], R);
-                    R = -R;
-#pragma unroll
-                    for (int mt = 0; mt < KT; ++mt) {
-                        const d4 av = *reinterpret_cast<const d4 *>(&pq[(16 * mt + c) * LDQ + 4 * g]);
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) Zp[mt] = mfma8(av[v], R[v], Zp[mt]);
-                    }
-                }
-            d4 G = {0., 0., 0., 0.};
-#pragma unroll
-            for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) G = mfma8(Zp[kt][v], Zp[kt][v], G);
-            eliminate_panel_d<DP>(G, Zp, pv, s, g, c);
-            const double sc = pv > 1.0e-280 ? rsqrt_d(pv) : 0.0;
-#pragma unroll
-            for (int mt = 0; mt < KT; ++mt) Zp[mt] *= sc;
-            if (P + 1 < KT) {
-                double *pp = panel(P);
-#pragma unroll
-                for (int mt = 0; mt < KT; ++mt)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) pp[(16 * mt + 4 * v + g) * LDQ + pc] = Zp[mt][v];
-            }
-        };
-#pragma unroll 1
-        for (int P = 0; P < KT; ++P) {
-            if (wave == P / NL) {
-                if (P % NL == 0)
-                    finish_panel(P, Z[0], piv[0]);
-                else
-                    finish_panel(P, Z[1], piv[1]);
-            }
-            __syncthreads();
-        }
-        double worst = 1.0;
-#pragma unroll
-        for (int nl = 0; nl < NL; ++nl) {
-            const double ratio = piv[nl] > 1.0e-280 ? norm2[nl] * rcp_d(piv[nl]) : 1.0;
-            worst = fmax(worst, ratio);
-        }
-#pragma unroll
-        for (int sft = 1; sft < 16; sft <<= 1) worst = fmax(worst, __shfl_xor(worst, sft, 64));
-        if (lane == 0) s.red[wave] = worst;
-        __syncthreads();
-        worst = fmax(fmax(s.red[0], s.red[1]), fmax(s.red[2], s.red[3]));
-        __syncthreads();
-        return worst;
-    };
+    auto qr_pass = [&](d4 (&Z)[NL][KT], double (&piv)[NL], double (&cexp)[NL]) { return wide_qr_pass(Z, piv, cexp, panel(0), s, wave, lane); };
     auto qr_in_place = [&](d4 (&Z)[NL][KT], const double (&colexp)[NL]) {
         double piv[NL], piv2[NL], ce[NL], ce2[NL];
         const double amp = qr_pass(Z, piv, ce);
@@ -1429,6 +1438,123 @@ template <int DP> __global__ __launch_bounds__(64) void lyap_step_kernel_d(StepA
     }
 }
 
+// The per-step estimator for 64 < d <= 128: a workgroup of four waves per step, the state's columns divided among
+// them as in reset_carry_wide_kernel, everything in double for both formats.
+template <typename IO> __global__ __launch_bounds__(256) void lyap_step_wide_kernel(const IO *J, const IO *S0, const IO *states, double *steplog,
+                                                                                    long long T, int d)
+{
+    constexpr int DP = 128, KT = 8, NL = 2, NW = 4, LDT = DP + 2, LDQ = 18;
+    constexpr int TQ = DP * DP / 4 / (NW * 64);
+    extern __shared__ __align__(32) unsigned char smem[];
+    double *tile = reinterpret_cast<double *>(smem);
+    double *panels = reinterpret_cast<double *>(smem);
+    WideScratch &s = *reinterpret_cast<WideScratch *>(smem + (size_t)KT * DP * LDQ * sizeof(double));
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+    const long long b = blockIdx.x / T, t = blockIdx.x % T;
+    auto is_odd = [](double im) { return ((int)rint(im * 0.318309886183790671538) & 1) != 0; };
+
+    // ---- input state, columns scaled to largest entry 1 (identity block past d), then its orthonormal factor
+    const IO *src = t == 0 ? (S0 ? S0 + (size_t)b * d * d * 2 : nullptr) : states + (size_t)(b * T + t - 1) * d * d * 2;
+    d4 Q[NL][KT];
+#pragma unroll
+    for (int nl = 0; nl < NL; ++nl) {
+        const int col = 32 * wave + 16 * nl + c;
+        double cmax = -__builtin_huge_val();
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * mt + 4 * v + g;
+                double r = row == col ? 0.0 : -__builtin_huge_val();
+                if (src && row < d && col < d) r = (double)src[((size_t)row * d + col) * 2];
+                Q[nl][mt][v] = r;
+                cmax = fmax(cmax, r);
+            }
+        cmax = fmax(cmax, __shfl_xor(cmax, 16, 64));
+        cmax = fmax(cmax, __shfl_xor(cmax, 32, 64));
+        const bool zero_col = !(cmax > -__builtin_huge_val());
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * mt + 4 * v + g;
+                const double tt = (Q[nl][mt][v] - cmax) * kLog2e;
+                double x = (zero_col || !(tt > -1000.0)) ? 0.0 : exp2(tt);
+                if (src && row < d && col < d && is_odd((double)src[((size_t)row * d + col) * 2 + 1])) x = -x;
+                Q[nl][mt][v] = x;
+            }
+    }
+    {
+        double piv[NL], ce[NL];
+        const double amp = wide_qr_pass(Q, piv, ce, panels, s, wave, lane);
+        if (amp > 1.0e3) (void)wide_qr_pass(Q, piv, ce, panels, s, wave, lane);
+    }
+
+    // ---- J_t as reals scaled by 2^-sh, sh from the largest entry; identity block past d
+    const IO *jp = J + (size_t)(b * T + t) * d * d * 2;
+    double jmax = -__builtin_huge_val();
+    for (int e = tid; e < d * d; e += NW * 64) jmax = fmax(jmax, (double)jp[(size_t)e * 2]);
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) jmax = fmax(jmax, __shfl_xor(jmax, sft, 64));
+    __syncthreads(); // (the panels of the factorisation above are done with; s.red is free)
+    if (lane == 0) s.red[wave] = jmax;
+    __syncthreads();
+    jmax = fmax(fmax(s.red[0], s.red[1]), fmax(s.red[2], s.red[3]));
+    const double sh = jmax > -__builtin_huge_val() ? ceil(jmax * kLog2e) : 0.0;
+    for (int q = 0; q < TQ; ++q) {
+        const int piece = tid + NW * 64 * q;
+        const int row = piece / (DP / 4), c4 = 4 * (piece % (DP / 4));
+        const int p4 = (c4 & ~15) | ((c4 >> 2) & 3);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            double x = (c4 + e == row) ? 1.0 : 0.0;
+            if (row < d && c4 + e < d) {
+                const IO *v = jp + ((size_t)row * d + c4 + e) * 2;
+                const double tt = __builtin_fma((double)v[0], kLog2e, -sh);
+                x = tt > -1000.0 ? exp2(tt) : 0.0;
+                if (is_odd((double)v[1])) x = -x;
+            }
+            tile[row * LDT + p4 + 4 * e] = x;
+        }
+    }
+    __syncthreads();
+    d4 Z[NL][KT];
+#pragma unroll
+    for (int nl = 0; nl < NL; ++nl)
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) Z[nl][mt] = d4{0., 0., 0., 0.};
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt) {
+            const d4 av = *reinterpret_cast<const d4 *>(&tile[(16 * mt + c) * LDT + 16 * kt + 4 * g]);
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int nl = 0; nl < NL; ++nl) Z[nl][mt] = mfma8(av[v], Q[nl][kt][v], Z[nl][mt]);
+        }
+    double piv[NL], piv2[NL], ce[NL], ce2[NL];
+    const double amp = wide_qr_pass(Z, piv, ce, panels, s, wave, lane); // (its first barrier comes after the reads of the tile)
+#pragma unroll
+    for (int nl = 0; nl < NL; ++nl) {
+        piv2[nl] = 1.0;
+        ce2[nl] = 0.0;
+    }
+    if (amp > 1.0e3) (void)wide_qr_pass(Z, piv2, ce2, panels, s, wave, lane);
+    if (g == 0) {
+#pragma unroll
+        for (int nl = 0; nl < NL; ++nl) {
+            const int col = 32 * wave + 16 * nl + c;
+            if (col < d) {
+                const bool ok = piv[nl] > 1.0e-280 && piv2[nl] > 1.0e-280;
+                steplog[(size_t)(b * T + t) * d + col] = ok ? 0.5 * (log(piv[nl]) + log(piv2[nl])) + (ce[nl] + ce2[nl] + sh) * kLn2 : -__builtin_huge_val();
+            }
+        }
+    }
+}
+
 // lambda[b][k] = scale * sum_t steplog[b][t][k], summed in a fixed order: kSlices slices of the
 // steps per batch item, partial sums in the workspace, then one block adds the slices.
 constexpr int kSlices = 64;
@@ -1438,25 +1564,29 @@ __global__ __launch_bounds__(256) void steplog_partial_kernel(const double *step
     __shared__ double red[256];
     const long long b = blockIdx.x / kSlices;
     const int slice = blockIdx.x % kSlices;
-    const int k = threadIdx.x & 63, r = threadIdx.x >> 6; // 4 groups of 64 threads; thread k < d owns exponent k
+    const int r = threadIdx.x >> 6; // 4 groups of 64 threads; thread k < d of a group owns exponent k (and k + 64 above 64)
     const long long per = (T + kSlices - 1) / kSlices;
     const long long lo = slice * per, hi = lo + per < T ? lo + per : T;
-    double acc = 0.0;
-    if (k < d)
-        for (long long t = lo + r; t < hi; t += 4) acc += steplog[(size_t)(b * T + t) * d + k];
-    red[threadIdx.x] = acc;
-    __syncthreads();
-    if (r == 0 && k < d) partial[(size_t)(b * kSlices + slice) * d + k] = ((red[k] + red[64 + k]) + red[128 + k]) + red[192 + k];
+    for (int k0 = 0; k0 < d; k0 += 64) { // (the same trips for every thread: there are barriers inside)
+        const int kk = threadIdx.x & 63, k = k0 + kk;
+        double acc = 0.0;
+        if (k < d)
+            for (long long t = lo + r; t < hi; t += 4) acc += steplog[(size_t)(b * T + t) * d + k];
+        __syncthreads();
+        red[threadIdx.x] = acc;
+        __syncthreads();
+        if (r == 0 && k < d) partial[(size_t)(b * kSlices + slice) * d + k] = ((red[kk] + red[64 + kk]) + red[128 + kk]) + red[192 + kk];
+    }
 }
 
 __global__ void steplog_final_kernel(const double *partial, double *lambda, int d, double scale)
 {
     const long long b = blockIdx.x;
-    const int k = threadIdx.x;
-    if (k >= d) return;
-    double acc = 0.0;
-    for (int sl = 0; sl < kSlices; ++sl) acc += partial[(size_t)(b * kSlices + sl) * d + k];
-    lambda[b * d + k] = acc * scale;
+    for (int k = threadIdx.x; k < d; k += blockDim.x) {
+        double acc = 0.0;
+        for (int sl = 0; sl < kSlices; ++sl) acc += partial[(size_t)(b * kSlices + sl) * d + k];
+        lambda[b * d + k] = acc * scale;
+    }
 }
 
 // Largest exponent from the final vector v = J_T ... J_1 u_0 (paper Section 4.2.2):
@@ -1561,8 +1691,19 @@ int launch_lyap_steps(goom_ctx *ctx, const void *J, const void *S0, const void *
     const long long grid = batch * T;
     if (grid > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
     const int dp = padded_dim(d);
-    if (dp > 64) return fail(ctx, GOOM_EUNSUPPORTED, "the per-step estimator supports d <= 64 (d=%d)", d);
+    if (d > 128) return fail(ctx, GOOM_EUNSUPPORTED, "the per-step estimator supports d <= 128 (d=%d)", d);
     prof_begin(ctx, "lyapunov_per_step_qr");
+    if (dp == 128) { // four waves per step
+        const size_t lds = (size_t)8 * 128 * 18 * sizeof(double) + sizeof(WideScratch);
+        const void *kern = dtype == GOOM_C64 ? reinterpret_cast<const void *>(lyap_step_wide_kernel<float>) : reinterpret_cast<const void *>(lyap_step_wide_kernel<double>);
+        if (int st = check_hip(ctx, hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "hipFuncSetAttribute(lyap_step_wide_kernel)")) return st;
+        if (dtype == GOOM_C64)
+            hipLaunchKernelGGL(lyap_step_wide_kernel<float>, dim3((unsigned)grid), dim3(256), lds, ctx->stream, static_cast<const float *>(J),
+                               static_cast<const float *>(S0), static_cast<const float *>(states), steplog, T, d);
+        else
+            hipLaunchKernelGGL(lyap_step_wide_kernel<double>, dim3((unsigned)grid), dim3(256), lds, ctx->stream, static_cast<const double *>(J),
+                               static_cast<const double *>(S0), static_cast<const double *>(states), steplog, T, d);
+    } else
     if (dtype == GOOM_C64) {
         StepArgs a;
         a.J = static_cast<const float *>(J);

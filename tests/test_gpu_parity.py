@@ -659,7 +659,7 @@ def test_lyapunov_spectrum_gaussian_closed_form(G, oracle):
 
 @pytest.mark.parametrize("T,d,L,policy,ctype", [(2048, 32, 0, 1, np.complex64), (1000, 8, 16, 1, np.complex64), (600, 16, 7, 0, np.complex64),
                                                 (300, 64, 16, 1, np.complex64), (1500, 32, 0, 1, np.complex128), (400, 10, 9, 0, np.complex128),
-                                                (200, 64, 16, 1, np.complex128)])
+                                                (200, 64, 16, 1, np.complex128), (96, 100, 12, 1, np.complex64), (64, 128, 16, 1, np.complex128)])
 def test_lyapunov_per_step_estimator(G, oracle, T, d, L, policy, ctype):
     # groups (b)-(d): two QRs per step on the selectively reset states; against the same groups in the
     # oracle (fed the oracle's own states) and against the sequential QR method
