@@ -269,7 +269,7 @@ size_t goom_scan_reset_workspace_bytes(int64_t T, int d, int64_t batch, int dtyp
  * method); a compound that does not contain X_0 carries no history, and resetting it discards the earlier
  * states' subspaces, which is why goom_scan_reset, not this call, serves the spectrum estimators.  O(T log T)
  * products.  states: [batch, T, d, d] (the paper's "Sums"); reset_flags: NULL or [batch, T] bytes, 1 where the
- * final value of a state descends from a reset.  Both formats, d <= 64.
+ * final value of a state descends from a reset.  Both formats, d <= 128.
  * workspace: goom_scan_reset_tree_workspace_bytes(...) bytes. */
 int goom_scan_reset_tree(goom_ctx *ctx, const void *J, const void *S0, void *states, uint8_t *reset_flags,
                          int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts, void *workspace,

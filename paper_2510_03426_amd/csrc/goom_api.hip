@@ -1157,7 +1157,7 @@ int goom_scan_reset(goom_ctx *ctx, const void *J, const void *S0, void *states, 
 
 size_t goom_scan_reset_tree_workspace_bytes(int64_t T, int d, int64_t batch, int dtype)
 {
-    if (T <= 0 || d <= 0 || batch <= 0 || d > 64 || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
+    if (T <= 0 || d <= 0 || batch <= 0 || d > GOOM_MAX_DIM || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
     return reset_tree_workspace_bytes(T, d, batch, dtype);
 }
 
@@ -1167,7 +1167,7 @@ int goom_scan_reset_tree(goom_ctx *ctx, const void *J, const void *S0, void *sta
     if (int s = check_common(ctx, dtype)) return s;
     if (!J || !states) return fail(ctx, GOOM_EINVAL, "null data pointer");
     if (T <= 0 || batch <= 0 || d <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive (T=%lld d=%d batch=%lld)", (long long)T, d, (long long)batch);
-    if (d > 64) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= 64 (d=%d)", d);
+    if (d > GOOM_MAX_DIM) return fail(ctx, GOOM_EUNSUPPORTED, "the reset scan supports d <= %d (d=%d)", GOOM_MAX_DIM, d);
     const int policy = opts ? opts->policy : GOOM_RESET_COLINEAR;
     if (policy < GOOM_RESET_NEVER || policy > GOOM_RESET_ALWAYS) return fail(ctx, GOOM_EINVAL, "unknown reset policy %d", policy);
     if (!aligned(J, 16) || (S0 && !aligned(S0, 16)) || !aligned(states, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");

@@ -765,6 +765,63 @@ __device__ double wide_qr_pass(d4 (&Z)[2][8], double (&piv)[2], double (&cexp)[2
     return worst;
 }
 
+// Is there a pair of columns of the 128 x 128 matrix Z (held by four waves as in wide_qr_pass) whose squared cosine
+// exceeds thr2?  Z goes to LDS panel by panel; every wave takes the pairs whose second column is its own.  The same
+// answer in every wave; all four waves must call this together.
+__device__ bool wide_colinear(const d4 (&Z)[2][8], double *panels, WideScratch &s, int wave, int lane, int d, double thr2)
+{
+    constexpr int DP = 128, KT = 8, NL = 2, LDQ = 18;
+    const int g = lane >> 4, c = lane & 15;
+    const int pc = ((c & 3) << 2) | (c >> 2);
+    auto panel = [&](int q) { return panels + (size_t)q * DP * LDQ; };
+    __syncthreads(); // the tile, or the panels of a factorisation, are free
+#pragma unroll
+    for (int nl = 0; nl < NL; ++nl) {
+        double *pp = panel(NL * wave + nl);
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) pp[(16 * mt + 4 * v + g) * LDQ + pc] = Z[nl][mt][v];
+        d4 Gd = {0., 0., 0., 0.};
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Gd = mfma8(Z[nl][kt][v], Z[nl][kt][v], Gd);
+        // G[j][j] for column j = 16 P + c sits in lane (c % 4, c), register c / 4
+        double dsel = Gd[0];
+        dsel = (c >> 2) == 1 ? Gd[1] : dsel;
+        dsel = (c >> 2) == 2 ? Gd[2] : dsel;
+        dsel = (c >> 2) == 3 ? Gd[3] : dsel;
+        if (g == (c & 3)) s.diag[32 * wave + 16 * nl + c] = dsel;
+    }
+    if (threadIdx.x == 0) s.hit = 0;
+    __syncthreads();
+    bool hit = false;
+#pragma unroll
+    for (int nl = 0; nl < NL; ++nl) {
+        const int P = NL * wave + nl;
+        const double dc = s.diag[16 * P + c];
+        for (int q = 0; q <= P; ++q) {
+            const double *pq = panel(q);
+            d4 Gt = {0., 0., 0., 0.}; // rows: columns 16 q + .. of Z, columns: 16 P + c
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) Gt = mfma8(pq[(16 * kt + 4 * v + g) * LDQ + pc], Z[nl][kt][v], Gt);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * q + 4 * v + g, col = 16 * P + c;
+                const double dr = s.diag[row];
+                const double x = Gt[v];
+                if (row < col && col < d && x * x > thr2 * dr * dc) hit = true;
+            }
+        }
+    }
+    if (__builtin_amdgcn_ballot_w64(hit) != 0 && lane == 0) s.hit = 1;
+    __syncthreads();
+    return s.hit != 0;
+}
+
 template <typename IO> __global__ __launch_bounds__(256) void reset_carry_wide_kernel(ResetArgs a)
 {
     constexpr int DP = 128, KT = DP / 16, NL = 2, NW = 4, LDT = DP + 2, LDQ = 18;
@@ -906,54 +963,7 @@ template <typename IO> __global__ __launch_bounds__(256) void reset_carry_wide_k
         if (boundary) {
             did_reset = a.policy == 1;
             if (!did_reset) {
-                // squared cosines between columns: Z goes to LDS panel by panel, every wave takes the pairs whose
-                // second column is its own
-                __syncthreads(); // the tile is free
-#pragma unroll
-                for (int nl = 0; nl < NL; ++nl) {
-                    double *pp = panel(NL * wave + nl);
-#pragma unroll
-                    for (int mt = 0; mt < KT; ++mt)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) pp[(16 * mt + 4 * v + g) * LDQ + pc] = Z[nl][mt][v];
-                    d4 Gd = {0., 0., 0., 0.};
-#pragma unroll
-                    for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) Gd = mfma8(Z[nl][kt][v], Z[nl][kt][v], Gd);
-                    double dsel = Gd[0];
-                    dsel = (c >> 2) == 1 ? Gd[1] : dsel;
-                    dsel = (c >> 2) == 2 ? Gd[2] : dsel;
-                    dsel = (c >> 2) == 3 ? Gd[3] : dsel;
-                    if (g == (c & 3)) s.diag[32 * wave + 16 * nl + c] = dsel;
-                }
-                if (tid == 0) s.hit = 0;
-                __syncthreads();
-                bool hit = false;
-                const double thr2 = (double)a.cos_threshold * (double)a.cos_threshold;
-#pragma unroll
-                for (int nl = 0; nl < NL; ++nl) {
-                    const int P = NL * wave + nl;
-                    const double dc = s.diag[16 * P + c];
-                    for (int q = 0; q <= P; ++q) {
-                        const double *pq = panel(q);
-                        d4 Gt = {0., 0., 0., 0.}; // rows: columns 16 q + .. of Z, columns: 16 P + c
-#pragma unroll
-                        for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) Gt = mfma8(pq[(16 * kt + 4 * v + g) * LDQ + pc], Z[nl][kt][v], Gt);
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            const int row = 16 * q + 4 * v + g, col = 16 * P + c;
-                            const double dr = s.diag[row];
-                            const double x = Gt[v];
-                            if (row < col && col < d && x * x > thr2 * dr * dc) hit = true;
-                        }
-                    }
-                }
-                if (__builtin_amdgcn_ballot_w64(hit) != 0 && lane == 0) s.hit = 1;
-                __syncthreads();
-                did_reset = s.hit != 0;
+                did_reset = wide_colinear(Z, panel(0), s, wave, lane, d, (double)a.cos_threshold * (double)a.cos_threshold);
             }
         }
         if (did_reset) {
@@ -1128,6 +1138,80 @@ template <int DP, typename IO> __global__ __launch_bounds__(64) void tree_reset_
                 }
             }
     if (lane == 0) a.flag[i] = 1;
+}
+
+// The same for 64 < d <= 128: four waves per element, the factorisation and the cosine test of the wide carry kernel.
+template <typename IO> __global__ __launch_bounds__(256) void tree_reset_wide_kernel(TreeResetArgs a)
+{
+    constexpr int DP = 128, KT = 8, NL = 2, LDQ = 18;
+    extern __shared__ __align__(32) unsigned char smem[];
+    double *panels = reinterpret_cast<double *>(smem);
+    WideScratch &s = *reinterpret_cast<WideScratch *>(smem + (size_t)KT * DP * LDQ * sizeof(double));
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+    const int d = a.d;
+    const long long i = blockIdx.x;
+    if (a.flag[i] || a.policy < 0) return; // whole workgroup
+    IO *mp = static_cast<IO *>(a.M) + (size_t)i * d * d * 2;
+    d4 Z[NL][KT];
+    bool any = false;
+#pragma unroll
+    for (int nl = 0; nl < NL; ++nl) {
+        const int col = 32 * wave + 16 * nl + c;
+        double cmax = -__builtin_huge_val();
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * mt + 4 * v + g;
+                double r = row == col ? 0.0 : -__builtin_huge_val();
+                if (row < d && col < d) {
+                    r = (double)mp[((size_t)row * d + col) * 2];
+                    any = any || r > -__builtin_huge_val();
+                }
+                Z[nl][mt][v] = r;
+                cmax = fmax(cmax, r);
+            }
+        cmax = fmax(cmax, __shfl_xor(cmax, 16, 64));
+        cmax = fmax(cmax, __shfl_xor(cmax, 32, 64));
+        const bool zero_col = !(cmax > -__builtin_huge_val());
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * mt + 4 * v + g;
+                double x = zero_col ? 0.0 : exp(Z[nl][mt][v] - cmax);
+                if (row < d && col < d && ((int)rint((double)mp[((size_t)row * d + col) * 2 + 1] * 0.318309886183790671538) & 1)) x = -x;
+                Z[nl][mt][v] = x;
+            }
+    }
+    if (tid == 0) s.hit = 0;
+    __syncthreads();
+    if (__builtin_amdgcn_ballot_w64(any) != 0 && lane == 0) s.hit = 1;
+    __syncthreads();
+    if (s.hit == 0) return; // a zero matrix is never selected (the same in every wave)
+    bool sel = a.policy == 1;
+    if (!sel) sel = wide_colinear(Z, panels, s, wave, lane, d, (double)a.cos_threshold * (double)a.cos_threshold);
+    if (!sel) return;
+    double piv[NL], ce[NL];
+    const double amp = wide_qr_pass(Z, piv, ce, panels, s, wave, lane);
+    if (amp > (sizeof(IO) == 4 ? 1.0e10 : 1.0e3)) (void)wide_qr_pass(Z, piv, ce, panels, s, wave, lane);
+    const IO pi = sizeof(IO) == 4 ? (IO)3.14159274101257324219f : (IO)3.14159265358979311600;
+#pragma unroll
+    for (int nl = 0; nl < NL; ++nl)
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * mt + 4 * v + g, col = 32 * wave + 16 * nl + c;
+                if (row < d && col < d) {
+                    const double q = Z[nl][mt][v];
+                    mp[((size_t)row * d + col) * 2] = (IO)(q != 0.0 ? log(fabs(q)) : -__builtin_huge_val());
+                    mp[((size_t)row * d + col) * 2 + 1] = q < 0.0 ? pi : (IO)0;
+                }
+            }
+    if (tid == 0) a.flag[i] = 1;
 }
 
 // After the products of a parallel step: element i = block * 2 half + half + u takes tmp[block][u] unless it is
@@ -1784,6 +1868,11 @@ template <typename IO> static int run_reset_tree_t(goom_ctx *ctx, const void *J,
     unsigned char *flags = tmp + align_up((size_t)n * mat, 256);
     const int dp = padded_dim(d);
     if (n > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
+    const size_t wide_lds = (size_t)8 * 128 * 18 * sizeof(double) + sizeof(WideScratch);
+    if (dp == 128)
+        if (int st = check_hip(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(tree_reset_wide_kernel<IO>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds),
+                               "hipFuncSetAttribute(tree_reset_wide_kernel)"))
+            return st;
     for (long long b = 0; b < batch; ++b) {
         IO *M = reinterpret_cast<IO *>(Mall + (size_t)b * n * mat);
         unsigned char *flag = flags + (size_t)b * n;
@@ -1800,7 +1889,8 @@ template <typename IO> static int run_reset_tree_t(goom_ctx *ctx, const void *J,
             prof_begin(ctx, "reset_tree_select_and_reset");
             if (dp == 16) hipLaunchKernelGGL((tree_reset_kernel<16, IO>), dim3((unsigned)n), dim3(64), 0, ctx->stream, a);
             else if (dp == 32) hipLaunchKernelGGL((tree_reset_kernel<32, IO>), dim3((unsigned)n), dim3(64), 0, ctx->stream, a);
-            else hipLaunchKernelGGL((tree_reset_kernel<64, IO>), dim3((unsigned)n), dim3(64), 0, ctx->stream, a);
+            else if (dp == 64) hipLaunchKernelGGL((tree_reset_kernel<64, IO>), dim3((unsigned)n), dim3(64), 0, ctx->stream, a);
+            else hipLaunchKernelGGL(tree_reset_wide_kernel<IO>, dim3((unsigned)n), dim3(256), wide_lds, ctx->stream, a);
             prof_end(ctx);
             if (int st = check_hip(ctx, hipGetLastError(), "launch tree_reset_kernel")) return st;
             // products of this parallel step: whole blocks, then the ragged last one

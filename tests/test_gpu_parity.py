@@ -554,7 +554,8 @@ def test_reset_scan_always_matches_sequential_oracle(G, oracle, T, d, L, ctype):
 
 @pytest.mark.parametrize("T,d,batch,ctype,policy,thr", [(11, 4, 2, np.complex128, 0, 0.9), (37, 8, 1, np.complex128, 0, 0.97), (64, 16, 1, np.complex128, 0, 0.9),
                                                         (23, 6, 2, np.complex64, 0, 0.9), (40, 32, 1, np.complex64, 0, 0.8), (9, 4, 1, np.complex64, -1, 0.9),
-                                                        (9, 4, 1, np.complex128, 1, 0.9), (33, 64, 1, np.complex128, 0, 0.7)])
+                                                        (9, 4, 1, np.complex128, 1, 0.9), (33, 64, 1, np.complex128, 0, 0.7), (12, 96, 1, np.complex128, 0, 0.5),
+                                                        (6, 128, 1, np.complex64, 1, 0.9)])
 def test_reset_scan_in_the_papers_tree_order(G, oracle, T, d, batch, ctype, policy, thr):
     """The selective-resetting transformation applied in the order of the paper's own parallel scan (Section 5, eq. 28;
     Appendix C) against the oracle's literal (A*, B*) tuples over reals in the same order.  Which compounds are reset is
