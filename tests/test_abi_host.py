@@ -68,7 +68,8 @@ def test_argument_validation_without_device(lib):
     assert lib.goom_scan(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), p, need) == EINVAL and "context" in err(lib)
     assert lib.goom_reduce(None, p, None, p, 4096, 8, 8, 1, 0, C.byref(o), None, 0) == EWS
     # the reset scan in the paper's tree order
-    assert lib.goom_scan_reset_tree(None, p, None, p, None, 64, 65, 1, 0, None, None, 0) == EUNSUP
+    assert lib.goom_scan_reset_tree(None, p, None, p, None, 64, 129, 1, 0, None, None, 0) == EUNSUP
+    assert lib.goom_scan_reset_tree(None, p, None, p, None, 64, 65, 1, 0, None, None, 0) == EWS
     assert lib.goom_scan_reset_tree(None, p, None, p, None, 64, 8, 1, 0, None, None, 0) == EWS
     assert lib.goom_scan_reset_tree_workspace_bytes(64, 8, 1, 0) >= 2 * 65 * 8 * 8 * 8
     # backward passes
