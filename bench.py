@@ -446,6 +446,18 @@ def lyapunov(g, torch, dev, si):
         "ms": round(sec * 1e3, 3), "jacobians_per_s": round(T / sec, 1),
         "kernels_ms": kernel_times(g, lambda: g.scan_reset(Jz))}
     del Jz
+    # the same estimator above 64 x 64 (four waves per batch item in the carry kernel): near-identity Jacobians
+    # I + 0.1 N(0, 1/d), d = 128, T = 16,384
+    T, d = 16384, 128
+    gen = si.device_generator(si.BASE_SEED + 5, dev)
+    Jw = torch.eye(d, device=dev)[None] + (0.1 / d ** 0.5) * torch.randn((T, d, d), device=dev, generator=gen)
+    Jz = g.to_goom(Jw)
+    del Jw
+    sec = timed(torch, lambda: g.lyapunov_spectrum(Jz, 0.01))
+    res["lyapunov_near_identity_d128_T16384"] = {
+        "ms": round(sec * 1e3, 3), "jacobians_per_s": round(T / sec, 1),
+        "kernels_ms": kernel_times(g, lambda: g.lyapunov_spectrum(Jz, 0.01))}
+    del Jz
     return res
 
 
