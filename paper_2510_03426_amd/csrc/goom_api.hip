@@ -142,12 +142,16 @@ static long long default_chunk_len(long long T, long long batch, long long reque
     // phase makes many chains cheap; chunks of at least 16 steps (8 at d = 32), 256 chains up to T = 2^14,
     // then 512, and the full round from T = 2^19 (2^16 at d = 32).  Up to twice as fast as the square-root rule
     // at T = 2^11 ... 2^12 and 5 - 20 % above it.
-    if (dtype == GOOM_C64 && (dp == 32 || dp == 64 || dp == 128)) {
+    // The same sweep with double components: chunks of at least 8 steps; 256 chains, from T = 2^14 on 512 at d = 64,
+    // from T = 2^13 on 1024 at d = 32 (T = 65 536: 4468 -> 3595 us at d = 64, 1623 -> 862 us at d = 32).
+    if (dp == 32 || dp == 64 || dp == 128) {
         long long want;
         if (dp == 128) want = 256;
-        else if (dp == 64) want = T < (1 << 15) ? 256 : T < (1 << 19) ? 512 : 1024;
-        else want = T < (1 << 14) ? 256 : T < (1 << 16) ? 512 : 1024;
-        const long long shortest = dp == 32 ? 8 : 16;
+        else if (dtype == GOOM_C64 && dp == 64) want = T < (1 << 15) ? 256 : T < (1 << 19) ? 512 : 1024;
+        else if (dtype == GOOM_C64) want = T < (1 << 14) ? 256 : T < (1 << 16) ? 512 : 1024;
+        else if (dp == 64) want = T < (1 << 14) ? 256 : 512;
+        else want = T < (1 << 13) ? 256 : 1024;
+        const long long shortest = (dtype == GOOM_C64 && dp != 32) ? 16 : 8;
         if (want > T / shortest) want = T / shortest;
         if (want < 1) want = 1;
         c = want < c_occ ? want : c_occ;
