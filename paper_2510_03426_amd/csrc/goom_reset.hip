@@ -703,26 +703,10 @@ __device__ double wide_qr_pass(d4 (&Z)[2][8], double (&piv)[2], double (&cexp)[2
         piv[nl] = 1.0;
     }
     __syncthreads(); // (whoever still read the LDS panels or the tile is done)
-    // one panel: orthogonal to the finished ones, twice (see qr_panels_d), then factorised and laid down
-    auto finish_panel = [&](int P, d4 (&Zp)[KT], double &pv) {
-#pragma unroll 1
-        for (int rep = 0; rep < 2; ++rep)
-#pragma unroll 1
-            for (int q = 0; q < P; ++q) {
-                const double *pq = panel(q);
-                d4 R = {0., 0., 0., 0.};
-#pragma unroll
-                for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) R = mfma8(pq[(16 * kt + 4 * v + g) * LDQ + pc], Zp[kt][v], R);
-                R = -R;
-#pragma unroll
-                for (int mt = 0; mt < KT; ++mt) {
-                    const d4 av = *reinterpret_cast<const d4 *>(&pq[(16 * mt + c) * LDQ + 4 * g]);
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) Zp[mt] = mfma8(av[v], R[v], Zp[mt]);
-                }
-            }
+    // Panel by panel: its owner factorises panel P (by then orthogonal to all finished ones) and lays it down; then
+    // every wave makes those of its own panels that come later orthogonal to it, twice in a row (one projection
+    // leaves rounding-level remainders of the panel's norm behind), all four waves at work at once.
+    auto factor_panel = [&](int P, d4 (&Zp)[KT], double &pv) {
         d4 G = {0., 0., 0., 0.};
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
@@ -740,16 +724,38 @@ __device__ double wide_qr_pass(d4 (&Z)[2][8], double (&piv)[2], double (&cexp)[2
                 for (int v = 0; v < 4; ++v) pp[(16 * mt + 4 * v + g) * LDQ + pc] = Zp[mt][v];
         }
     };
+    auto project_out = [&](int P, d4 (&Zp)[KT]) {
+        const double *pq = panel(P);
+#pragma unroll 1
+        for (int rep = 0; rep < 2; ++rep) {
+            d4 R = {0., 0., 0., 0.};
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) R = mfma8(pq[(16 * kt + 4 * v + g) * LDQ + pc], Zp[kt][v], R);
+            R = -R;
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) {
+                const d4 av = *reinterpret_cast<const d4 *>(&pq[(16 * mt + c) * LDQ + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) Zp[mt] = mfma8(av[v], R[v], Zp[mt]);
+            }
+        }
+    };
 #pragma unroll 1
     for (int P = 0; P < KT; ++P) {
         if (wave == P / NL) {
             if (P % NL == 0)
-                finish_panel(P, Z[0], piv[0]);
+                factor_panel(P, Z[0], piv[0]);
             else
-                finish_panel(P, Z[1], piv[1]);
+                factor_panel(P, Z[1], piv[1]);
         }
         __syncthreads();
+        if (NL * wave > P) project_out(P, Z[0]);
+        if (NL * wave + 1 > P) project_out(P, Z[1]);
+        // (no barrier: the next panel is written elsewhere, and its owner reads nothing but its own registers before)
     }
+    __syncthreads();
     double worst = 1.0;
 #pragma unroll
     for (int nl = 0; nl < NL; ++nl) {
