@@ -185,9 +185,11 @@ size_t goom_scan_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dty
  * loops, harnesses that forbid hipMalloc): the scan's workspace is a static array of
  * GOOM_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process ends; the call
  * itself allocates nothing.  Arguments and results as for goom_scan (same kernels, same launch plan,
- * bit-identical outputs).  A scan whose goom_scan_workspace_bytes(...) exceeds GOOM_STATIC_SCRATCH_BYTES is
- * rejected with GOOM_EWORKSPACE and nothing is enqueued (the T = 2^20, d = 64 complex64 scan needs 36.2 MB
- * and fits).  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * bit-identical outputs).  If the default plan (opts NULL or chunk_len 0) needs more than the array holds,
+ * the shortest chunk length among 8, 16, 32, ... whose plan fits is taken instead (the outputs are then those of
+ * goom_scan with that chunk_len).  A scan whose goom_scan_workspace_bytes(...) still exceeds
+ * GOOM_STATIC_SCRATCH_BYTES is rejected with GOOM_EWORKSPACE and nothing is enqueued (the T = 2^20, d = 64
+ * complex64 scan needs 36.2 MB and fits).  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
  * streams, two contexts, two threads) race on it and must be serialised by the caller.  Nothing in the array
  * has to be cleared between calls: every phase writes what the next one reads. */
 #define GOOM_STATIC_SCRATCH_BYTES (40u << 20)

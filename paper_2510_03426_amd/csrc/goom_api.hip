@@ -799,14 +799,29 @@ int goom_scan_static(goom_ctx *ctx, const void *M, const void *init, void *P, in
 {
     // argument errors first (reported without a device); the size check uses the same plan as goom_scan
     if (int s = check_scan_args(ctx, M, P, T, d, m, batch, dtype, opts, GOOM_MAX_DIM_LMME)) return s;
-    const size_t need = goom_scan_workspace_bytes(T, d, m, batch, dtype, opts);
+    goom_scan_opts eff = opts ? *opts : goom_scan_opts{0, 0};
+    size_t need = goom_scan_workspace_bytes(T, d, m, batch, dtype, &eff);
+    if (need > (size_t)GOOM_STATIC_SCRATCH_BYTES && eff.chunk_len == 0) {
+        // the default plan has more chunks than the array holds products of: the shortest chunks, by powers of two,
+        // that fit (fewer chunks, a smaller workspace; the result is the same scan)
+        for (long long L = 8; L < T; L *= 2) {
+            goom_scan_opts longer = eff;
+            longer.chunk_len = L;
+            const size_t n = goom_scan_workspace_bytes(T, d, m, batch, dtype, &longer);
+            if (n > 0 && n <= (size_t)GOOM_STATIC_SCRATCH_BYTES) {
+                eff = longer;
+                need = n;
+                break;
+            }
+        }
+    }
     if (need > (size_t)GOOM_STATIC_SCRATCH_BYTES)
         return fail(ctx, GOOM_EWORKSPACE, "this scan needs %zu bytes of scratch memory; goom_scan_static holds %zu (use goom_scan with a workspace)",
                     need, (size_t)GOOM_STATIC_SCRATCH_BYTES);
     if (!ctx) return fail(nullptr, GOOM_EINVAL, "null context");
     if (!ctx->scratch) return fail(ctx, GOOM_EHIP, "%s", ctx->scratch_error.empty() ? "static scratch memory unavailable" : ctx->scratch_error.c_str());
     // nothing in the workspace has to start at zero: every phase writes what the next one reads
-    return run_scan(ctx, M, init, P, T, d, m, batch, dtype, opts, ctx->scratch, (size_t)GOOM_STATIC_SCRATCH_BYTES, false);
+    return run_scan(ctx, M, init, P, T, d, m, batch, dtype, &eff, ctx->scratch, (size_t)GOOM_STATIC_SCRATCH_BYTES, false);
 }
 
 int goom_reduce(goom_ctx *ctx, const void *M, const void *init, void *P_final, int64_t T, int d, int m, int64_t batch,

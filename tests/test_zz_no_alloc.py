@@ -36,6 +36,22 @@ def test_scan_static_matches_scan_on_two_calls_in_a_row():
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), \
             f"{np.sum(a.view(np.uint32) != b.view(np.uint32))} words differ from goom_scan"
         assert np.isfinite(a.real).all() and a.real.max() > 100.0  # the outputs are real results, past float range soon
+    # a default plan that does not fit the array: the call takes the shortest longer chunks that do
+    T, d = 4096, 128
+    x = si.normal_chain(si.BASE_SEED + 47, T, d).astype(np.float64)
+    z = g.to_goom(torch.from_numpy(x).cuda())
+    assert z.dtype == torch.complex128
+    assert g.lib.goom_scan_workspace_bytes(T, d, d, 1, 1, C.byref(ScanOpts(0, 0))) > g.STATIC_SCRATCH_BYTES
+    L = 8
+    while g.lib.goom_scan_workspace_bytes(T, d, d, 1, 1, C.byref(ScanOpts(L, 0))) > g.STATIC_SCRATCH_BYTES:
+        L *= 2
+    print(f"goom_scan_static: T={T} d={d} complex128, default plan too large, chunk_len {L} fits", flush=True)
+    ref = g.scan(z, chunk_len=L)
+    out = torch.empty_like(ref)
+    g.scan_static(z, out)
+    torch.cuda.synchronize()
+    a, b = out.cpu().numpy(), ref.cpu().numpy()
+    assert np.array_equal(a.view(np.uint64), b.view(np.uint64))
     # a scan whose workspace exceeds the array is refused, with nothing enqueued
     T, d = 1 << 16, 128
     big = torch.empty(1, dtype=torch.complex64, device="cuda")  # never dereferenced: the call fails on the host
