@@ -292,6 +292,13 @@ def test_lmme_repair_when_few_terms_decide(G, oracle):
     got = host(G.lmme(dev(A), dev(B), flags=LMME_EXACT))
     assert np.isneginf(got.real[:, 5, :]).all()
     compare(got, re, sg, kap, name="lmme ragged with zeros", max_ill_fraction=0.01)
+    # ragged sizes with at most 128 inner indices: the path that orders the terms by keys, at the operands' edges
+    for (b2, n2, d2, m2) in ((2, 70, 100, 90), (1, 130, 128, 65), (3, 64, 17, 64)):
+        A3, B3 = si.wide_range_goom_pairs(si.BASE_SEED + 272 + d2, b2, n2, d2, m2, sigma=200.0, dtype=np.complex64)
+        A3.real[rng.random(A3.shape) < 0.1] = -np.inf
+        re3, sg3, kap3 = oracle.lmme(A3, B3, return_kappa=True)
+        got3 = host(G.lmme(dev(A3), dev(B3), flags=LMME_EXACT))
+        compare(got3, re3, sg3, kap3, name=f"lmme ragged, keyed {n2}x{d2}x{m2}", max_ill_fraction=0.01)
     # two leading terms of opposite sign, half a unit apart: inner indices 0 and 1 tower over the others
     A2, B2 = A[:1].copy(), B[:1].copy()
     A2[0, :, 0] = 900.0
