@@ -236,6 +236,9 @@ template <int DP> struct WaveD {
     double rperm[2][16];  // the same in perm16 order
     double qcol[2][DP];   // column k of the panel at step k, rows in perm16 order
     double diag[DP];      // diagonal of the Gram matrix (selection by cosines)
+    double brow[4][16];   // blocked elimination: the four pivot rows of a block, entry j at position j
+    double bperm[4][16];  // the same in perm16 order
+    double bcol[4][DP];   // the four pivot columns of the panel, rows in perm16 order
     double qpanel[DP / 16 > 1 ? DP / 16 - 1 : 1][DP * LDQ]; // finished panels of Q: [row][column within the panel, perm16 order]
 };
 
@@ -294,6 +297,71 @@ template <int DP, typename S> __device__ void eliminate_panel_d(d4 &G, d4 (&Zp)[
         for (int mt = 0; mt < KT; ++mt) {
             const d4 zk = *reinterpret_cast<const d4 *>(&qcol[16 * mt + 4 * g]);
             Zp[mt] -= zk * tj;
+        }
+    }
+    wave_sync();
+}
+
+// The same elimination four pivots at a time (panels of up to 32 rows): the four pivot rows of the Gram matrix and
+// the four pivot columns of the panel make one trip through LDS, and every lane then carries out the four steps on
+// copies of its own (the 4 x 4 block on the diagonal, the pivot rows at its own column and at the columns whose
+// numbers are its rows', the pivot columns at its rows): the same multiply-adds on the same numbers in the same
+// order as one pivot at a time, four times fewer waits for LDS.
+template <int DP> __device__ void eliminate_panel_blocked(d4 &G, d4 (&Zp)[DP / 16], double &piv, WaveD<DP> &s, int g, int c)
+{
+    constexpr int KT = DP / 16;
+    const int pc = ((c & 3) << 2) | (c >> 2);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        wave_sync();
+        // row 4 b + g of the Gram matrix at column c; columns 4 b + j of the panel (from the lanes that hold them)
+        s.brow[g][c] = G[b];
+        s.bperm[g][pc] = G[b];
+        if ((c >> 2) == b) {
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) *reinterpret_cast<d4 *>(&s.bcol[c & 3][16 * mt + 4 * g]) = Zp[mt];
+        }
+        wave_sync();
+        double a[4];   // pivot row j at this lane's column
+        d4 P[4];       // pivot row j at columns 4 v + g
+        d4 B[4];       // pivot row j at columns 4 b + i
+        d4 zb[4][KT];  // pivot column j at this lane's rows
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            a[j] = s.brow[j][c];
+            P[j] = *reinterpret_cast<const d4 *>(&s.bperm[j][4 * g]);
+            B[j] = *reinterpret_cast<const d4 *>(&s.brow[j][4 * b]);
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) zb[j][mt] = *reinterpret_cast<const d4 *>(&s.bcol[j][16 * mt + 4 * g]);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k = 4 * b + j;
+            const double pivot = B[j][j];
+            if (c == k) piv = pivot;
+            const double inv = pivot > 1.0e-280 ? rcp_d(pivot) : 0.0;
+            // row k beyond the pivot, as the one-pivot form stores it: zero up to and including column k
+            const double rc = c > k ? a[j] : 0.0;
+            const double tj = rc * inv;
+            d4 ri;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ri[v] = (4 * v + g > k) ? P[j][v] : 0.0;
+            const d4 rinv = ri * inv; // (row k times 1 / pivot: the multipliers of the columns 4 v + g)
+            G -= ri * tj;
+#pragma unroll
+            for (int mt = 0; mt < KT; ++mt) Zp[mt] -= zb[j][mt] * tj;
+            // the later pivot rows and columns of the block, brought up to date the same way
+#pragma unroll
+            for (int i = j + 1; i < 4; ++i) {
+                const double rki = B[j][i];         // row k at column 4 b + i (> k)
+                const double ti = rki * inv;        // the multiplier of column 4 b + i
+                a[i] -= rki * tj;                   // entry (4 b + i, c): row factor times this column's multiplier
+                P[i] -= rinv * rki;                 // entries (4 b + i, 4 v + g): row factor times those columns' multipliers
+#pragma unroll
+                for (int i2 = j + 1; i2 < 4; ++i2) B[i][i2] -= rki * (B[j][i2] * inv);
+#pragma unroll
+                for (int mt = 0; mt < KT; ++mt) zb[i][mt] -= zb[j][mt] * ti;
+            }
         }
     }
     wave_sync();
@@ -359,7 +427,10 @@ template <int DP> __device__ double qr_panels_d(d4 (&Z)[DP / 16][DP / 16], doubl
 #pragma unroll
             for (int v = 0; v < 4; ++v) G = mfma8(Z[p][kt][v], Z[p][kt][v], G);
         piv[p] = 1.0;
-        eliminate_panel_d<DP>(G, Z[p], piv[p], s, g, c);
+        if constexpr (DP <= 32)
+            eliminate_panel_blocked<DP>(G, Z[p], piv[p], s, g, c);
+        else
+            eliminate_panel_d<DP>(G, Z[p], piv[p], s, g, c);
         const double sc = piv[p] > 1.0e-280 ? rsqrt_d(piv[p]) : 0.0;
 #pragma unroll
         for (int mt = 0; mt < KT; ++mt) Z[p][mt] *= sc;
