@@ -236,9 +236,11 @@ template <int DP> struct WaveD {
     double rperm[2][16];  // the same in perm16 order
     double qcol[2][DP];   // column k of the panel at step k, rows in perm16 order
     double diag[DP];      // diagonal of the Gram matrix (selection by cosines)
-    double brow[4][16];   // blocked elimination: the four pivot rows of a block, entry j at position j
-    double bperm[4][16];  // the same in perm16 order
-    double bcol[4][DP];   // the four pivot columns of the panel, rows in perm16 order
+    // blocked elimination (panels of up to 32 rows only): the four pivot rows of a block, entry j at position j; the
+    // same in perm16 order; the four pivot columns of the panel, rows in perm16 order
+    double brow[DP <= 32 ? 4 : 1][16];
+    double bperm[DP <= 32 ? 4 : 1][16];
+    double bcol[DP <= 32 ? 4 : 1][DP];
     double qpanel[DP / 16 > 1 ? DP / 16 - 1 : 1][DP * LDQ]; // finished panels of Q: [row][column within the panel, perm16 order]
 };
 
