@@ -162,23 +162,39 @@ template <typename R, int NW> __global__ __launch_bounds__(NW * 64) void bwd_pre
 
 // The same without the copy of the matrices, for the scan kernels that read A transposed and in reverse order
 // themselves: only the shift of step s's log-magnitudes, shift[b, s] = c_t - c_{t+1} (-inf for s = 0: the zero
-// matrix), and gt.  One wave per (b, s).
+// matrix), and gt.  A group of lanes per (b, s), so that a wave serves two to eight steps of short vectors.
 template <typename R> __global__ __launch_bounds__(256) void bwd_shift_kernel(const typename C2<R>::type *__restrict__ H, const R *__restrict__ G,
                                                                              float *__restrict__ shift, typename C2<R>::type *__restrict__ gt,
-                                                                             long long T, int d, long long nsteps)
+                                                                             long long T, int d, long long nsteps, int group)
 {
+    // a group of `group` lanes (8, 16, 32 or 64: the power of two that holds d, or the whole wave) per (b, s)
     typedef typename C2<R>::type c2;
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const long long step = (long long)blockIdx.x * 4 + wave;
-    if (step >= nsteps) return; // whole wave
-    const long long b = step / T, s = step % T;
+    const int lane = threadIdx.x & 63, sub = lane % group;
+    const long long step = ((long long)blockIdx.x * 256 + threadIdx.x) / group;
+    const bool active = step < nsteps;
+    const long long b = active ? step / T : 0, s = active ? step % T : 0;
     const R ninf = sizeof(R) == 4 ? (R)-__builtin_huge_valf() : (R)-__builtin_huge_val();
     const long long t = T - 1 - s;
-    const R ct = state_scale<R>(H + (size_t)(b * T + t) * d, d);
-    const R delta = s == 0 ? ninf : ct - state_scale<R>(H + (size_t)(b * T + t + 1) * d, d);
-    if (lane == 0) shift[b * T + s] = (float)delta;
-    for (int i = lane; i < d; i += 64) {
+    // c_t and c_{t+1}: the whole numbers nearest the largest log-magnitudes of h_t and h_{t+1} (0 for a zero state)
+    auto scale_of = [&](long long tt) {
+        R top = ninf;
+        if (active && tt < T)
+            for (int i = sub; i < d; i += group) {
+                const R v = H[(size_t)(b * T + tt) * d + i].x;
+                top = v > top ? v : top;
+            }
+        for (int sft = group >> 1; sft > 0; sft >>= 1) {
+            const R o = __shfl_xor(top, sft, 64);
+            top = o > top ? o : top;
+        }
+        const bool finite = top > ninf && top < -ninf;
+        return finite ? (R)__builtin_rint((double)top) : (R)0;
+    };
+    const R ct = scale_of(t);
+    const R cnext = scale_of(t + 1);
+    if (!active) return;
+    if (sub == 0) shift[b * T + s] = s == 0 ? (float)ninf : (float)(ct - cnext);
+    for (int i = sub; i < d; i += group) {
         const R gv = G[(size_t)(b * T + t) * d + i];
         const c2 h = H[(size_t)(b * T + t) * d + i];
         c2 o;
@@ -360,8 +376,10 @@ template <typename R> static int bwd_shift_t(goom_ctx *ctx, const void *H, const
     typedef typename C2<R>::type c2;
     const long long nsteps = batch * T;
     prof_begin(ctx, "affine_backward_prepare_operands");
-    hipLaunchKernelGGL(bwd_shift_kernel<R>, dim3((unsigned)((nsteps + 3) / 4)), dim3(256), 0, ctx->stream, static_cast<const c2 *>(H),
-                       static_cast<const R *>(G), shift, static_cast<c2 *>(gt), T, d, nsteps);
+    const int group = d <= 8 ? 8 : d <= 16 ? 16 : d <= 32 ? 32 : 64;
+    const long long per_block = 256 / group;
+    hipLaunchKernelGGL(bwd_shift_kernel<R>, dim3((unsigned)((nsteps + per_block - 1) / per_block)), dim3(256), 0, ctx->stream, static_cast<const c2 *>(H),
+                       static_cast<const R *>(G), shift, static_cast<c2 *>(gt), T, d, nsteps, group);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch bwd_shift_kernel");
 }
