@@ -950,3 +950,49 @@ ORACLE_API void oracle_affine_backward(const double *are, const uint8_t *asg, co
     free(z);
     free(s);
 }
+
+/* Backward pass of C' = LMME(A', B') over GOOMs (Section 3.2 with the derivatives of Section 3.1 in the limit
+ * eps -> 0, as for the recurrence above).  With C = A B over reals and upstream gradients G_ik = dL / d Re C'_ik,
+ * d log|C_ik| / d A_ij = B_jk / C_ik and d A_ij / d log|A_ij| = A_ij, so
+ *     dL / d Re A'_ij = sum_k G_ik A_ij B_jk / C_ik,      dL / d Re B'_jk = sum_i G_ik A_ij B_jk / C_ik,
+ * each term evaluated as (+-) exp(A'_ij + B'_jk - C'_ik + log|G_ik|) and the sums taken relative to their largest
+ * term in long double.  An output C_ik that is exactly zero passes no gradient.  A [n, d], B [d, m], C = LMME(A, B)
+ * [n, m] in working form, G [n, m] reals; gA [n, d], gB [d, m] reals. */
+ORACLE_API void oracle_lmme_backward(const double *are, const uint8_t *asg, const double *bre, const uint8_t *bsg,
+                                     const double *cre, const uint8_t *csg, const double *g, double *gA, double *gB,
+                                     int n, int d, int m)
+{
+    const int len = n > m ? n : m;
+    double *z = (double *)malloc(sizeof(double) * (size_t)(len > 0 ? len : 1));
+    uint8_t *s = (uint8_t *)malloc((size_t)(len > 0 ? len : 1));
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < d; ++j) {
+            for (int k = 0; k < m; ++k) {
+                const double a = are[(size_t)i * d + j], b = bre[(size_t)j * m + k], c = cre[(size_t)i * m + k], gv = g[(size_t)i * m + k];
+                const int live = a > -INFINITY && b > -INFINITY && c > -INFINITY && gv != 0.0;
+                z[k] = live ? (double)((long double)a + (long double)b - (long double)c + logl(fabsl((long double)gv))) : -INFINITY;
+                s[k] = (uint8_t)(asg[(size_t)i * d + j] ^ bsg[(size_t)j * m + k] ^ csg[(size_t)i * m + k] ^ (gv < 0.0));
+            }
+            double re;
+            uint8_t sg;
+            signed_lse(m, z, s, &re, &sg, NULL);
+            const double v = re > -INFINITY ? (double)expl((long double)re) : 0.0;
+            gA[(size_t)i * d + j] = sg ? -v : v;
+        }
+    for (int j = 0; j < d; ++j)
+        for (int k = 0; k < m; ++k) {
+            for (int i = 0; i < n; ++i) {
+                const double a = are[(size_t)i * d + j], b = bre[(size_t)j * m + k], c = cre[(size_t)i * m + k], gv = g[(size_t)i * m + k];
+                const int live = a > -INFINITY && b > -INFINITY && c > -INFINITY && gv != 0.0;
+                z[i] = live ? (double)((long double)a + (long double)b - (long double)c + logl(fabsl((long double)gv))) : -INFINITY;
+                s[i] = (uint8_t)(asg[(size_t)i * d + j] ^ bsg[(size_t)j * m + k] ^ csg[(size_t)i * m + k] ^ (gv < 0.0));
+            }
+            double re;
+            uint8_t sg;
+            signed_lse(n, z, s, &re, &sg, NULL);
+            const double v = re > -INFINITY ? (double)expl((long double)re) : 0.0;
+            gB[(size_t)j * m + k] = sg ? -v : v;
+        }
+    free(z);
+    free(s);
+}

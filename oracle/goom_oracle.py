@@ -261,6 +261,27 @@ def affine_scan_backward(a, b, grad_h, h0=None, h=None):
     return gA, gb, gh0, (lre, lsg)
 
 
+def lmme_backward(a, b, grad_c, c=None):
+    """Backward pass of C' = LMME(A', B') (Sections 3.1, 3.2): given grad_c[..., i, k] = dL / d Re C'_ik, returns
+    (dL / d Re A', dL / d Re B') as reals.  a: [..., n, d], b: [..., d, m]; c: the forward result to use (default:
+    computed here by the definition)."""
+    are, asg = _as_working(a)
+    bre, bsg = _as_working(b)
+    n, d = are.shape[-2:]
+    m = bre.shape[-1]
+    lead = are.shape[:-2]
+    batch = int(np.prod(lead)) if lead else 1
+    cre, csg = lmme(a, b) if c is None else _as_working(c)
+    G = _c(grad_c, np.float64)
+    assert G.shape == lead + (n, m) and bre.shape == lead + (d, m)
+    gA = np.empty(lead + (n, d)); gB = np.empty(lead + (d, m))
+    v = lambda x: x.reshape((batch,) + x.shape[len(lead):])
+    for q in range(batch):
+        lib().oracle_lmme_backward(_p(v(are)[q]), _p(v(asg)[q]), _p(v(bre)[q]), _p(v(bsg)[q]), _p(v(cre)[q]), _p(v(csg)[q]),
+                                   _p(v(G)[q]), _p(v(gA)[q]), _p(v(gB)[q]), C.c_int(n), C.c_int(d), C.c_int(m))
+    return gA, gB
+
+
 def to_goom_backward(x, grad_re, eps: float):
     """Backward of float -> GOOM with the redefined derivatives of Section 3.1: grad_re * s(x) / (|x| + eps)."""
     x = _c(x, np.float64); g = _c(grad_re, np.float64)

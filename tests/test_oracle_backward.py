@@ -116,3 +116,75 @@ def test_codec_backward_redefined_derivatives(oracle):
     assert np.allclose(gz, want, rtol=1e-14) and np.all(gz != 0)
     # and the ordinary derivative of +-exp(re) with respect to re when eps = 0
     assert np.allclose(oracle.from_goom_backward(z[[0, 1, 4]], np.ones(3), 0.0), [3.0, -3.0, math.exp(1.5)], rtol=1e-15)
+
+
+def lmme_loss_value_domain(A, B, G):
+    """L = sum_ik G[i, k] log|(A B)[i, k]| in long double reals."""
+    Cm = (A.astype(np.longdouble)[:, :, None] * B.astype(np.longdouble)[None, :, :]).sum(axis=1)
+    return (G.astype(np.longdouble) * np.log(np.abs(Cm))).sum()
+
+
+def test_lmme_backward_against_finite_differences(oracle):
+    rng = np.random.default_rng(41)
+    n, d, m = 5, 7, 4
+    A = rng.standard_normal((n, d)) * np.exp(rng.uniform(-3, 3, (n, d)))
+    B = rng.standard_normal((d, m)) * np.exp(rng.uniform(-3, 3, (d, m)))
+    G = rng.standard_normal((n, m))
+    gA, gB = oracle.lmme_backward(goom_of(A), goom_of(B), G)
+    delta = 1e-5
+    for (i, j) in [(0, 0), (4, 6), (2, 3), (1, 5), (3, 1)]:
+        Ap, Am = A.copy(), A.copy()
+        Ap[i, j] *= math.exp(delta)
+        Am[i, j] *= math.exp(-delta)
+        fd = float((lmme_loss_value_domain(Ap, B, G) - lmme_loss_value_domain(Am, B, G)) / (2 * delta))
+        assert abs(gA[i, j] - fd) < 1e-7 * max(1.0, abs(fd)), (i, j, gA[i, j], fd)
+    for (j, k) in [(0, 0), (6, 3), (3, 2), (5, 1), (1, 0)]:
+        Bp, Bm = B.copy(), B.copy()
+        Bp[j, k] *= math.exp(delta)
+        Bm[j, k] *= math.exp(-delta)
+        fd = float((lmme_loss_value_domain(A, Bp, G) - lmme_loss_value_domain(A, Bm, G)) / (2 * delta))
+        assert abs(gB[j, k] - fd) < 1e-7 * max(1.0, abs(fd)), (j, k, gB[j, k], fd)
+    # a transposed operand would pass the square case only: the shapes here are all different
+
+
+def test_lmme_backward_sum_rules_and_special_cases(oracle):
+    rng = np.random.default_rng(42)
+    n, d, m = 6, 9, 8
+    A = goom_of(rng.standard_normal((n, d))) + rng.uniform(-4000, 4000, (n, 1))  # rows far outside float range
+    B = goom_of(rng.standard_normal((d, m))) + rng.uniform(-4000, 4000, (1, m))
+    G = rng.standard_normal((n, m))
+    gA, gB = oracle.lmme_backward(A, B, G)
+    # scaling row i of A by e^s adds s to row i of log|C|: the gradients of a row of A' add up to those of the row of C';
+    # likewise for the columns of B'
+    assert np.allclose(gA.sum(axis=1), G.sum(axis=1), rtol=1e-9, atol=1e-11)
+    assert np.allclose(gB.sum(axis=0), G.sum(axis=0), rtol=1e-9, atol=1e-11)
+    # scaling column j of A by e^s and row j of B by e^-s changes nothing
+    assert np.allclose(gA.sum(axis=0), gB.sum(axis=1), rtol=1e-9, atol=1e-11)
+    # the row and column shifts themselves change no gradient
+    gA0, gB0 = oracle.lmme_backward(goom_of(np.exp(A.real - A.real.max(axis=1, keepdims=True)) * np.cos(A.imag)),
+                                    goom_of(np.exp(B.real - B.real.max(axis=0, keepdims=True)) * np.cos(B.imag)), G)
+    assert np.allclose(gA, gA0, rtol=1e-8, atol=1e-10) and np.allclose(gB, gB0, rtol=1e-8, atol=1e-10)
+    # inner dimension 1: C_ik = a_i b_k, so every term is G_ik itself
+    a1, b1 = goom_of(np.array([[2.0], [-3.0]])), goom_of(np.array([[0.5, -4.0, 7.0]]))
+    G1 = np.array([[1.0, 2.0, 3.0], [10.0, 20.0, 30.0]])
+    gA1, gB1 = oracle.lmme_backward(a1, b1, G1)
+    assert np.allclose(gA1[:, 0], [6.0, 60.0]) and np.allclose(gB1[0], [11.0, 22.0, 33.0])
+    # identity right operand: C = A, the gradient goes straight through; that of B' is G_ik A_ij / A_ik summed over i
+    Av = rng.standard_normal((3, 3)) + 2.0
+    gA2, gB2 = oracle.lmme_backward(goom_of(Av), goom_of(np.eye(3)), np.ones((3, 3)))
+    assert np.allclose(gA2, np.ones((3, 3)))
+    assert np.allclose(gB2, np.eye(3) * 3.0)  # off-diagonal entries of B are zero: log-domain gradient A_ij B_jk / C_ik = 0
+    # zero entries of the operands and zero gradients pass nothing; an exactly zero output passes nothing
+    Az = np.array([[1.0, 0.0], [1.0, -1.0]])
+    Bz = np.array([[1.0, 2.0], [1.0, 3.0]])
+    gA3, gB3 = oracle.lmme_backward(goom_of(Az), goom_of(Bz), np.array([[1.0, 1.0], [5.0, 1.0]]))  # C[1, 0] = 0 exactly
+    assert gA3[0, 1] == 0.0 and np.isfinite(gA3).all() and np.isfinite(gB3).all()
+    assert np.allclose(gA3[0], [2.0, 0.0])
+    assert np.allclose(gA3[1], [2.0 / -1.0, -3.0 / -1.0])  # only C[1, 1] = 2 - 3 = -1 contributes
+    # batched leading axes
+    Ab = goom_of(rng.standard_normal((2, 3, 4, 5)))
+    Bb = goom_of(rng.standard_normal((2, 3, 5, 2)))
+    Gb = rng.standard_normal((2, 3, 4, 2))
+    gAb, gBb = oracle.lmme_backward(Ab, Bb, Gb)
+    gAq, gBq = oracle.lmme_backward(Ab[1, 2], Bb[1, 2], Gb[1, 2])
+    assert np.array_equal(gAb[1, 2], gAq) and np.array_equal(gBb[1, 2], gBq)
