@@ -414,7 +414,15 @@ def batched_lmme(g, torch, dev, si):
             "ms": round(sec * 1e3, 3), "tflops": round(2.0 * n ** 3 * B / sec / 1e12, 2),
             "pct_of_mfma_peak": round(100 * 2.0 * n ** 3 * B / sec / 1e12 / peak, 2),
             "hbm_gbs": round(3 * a.numel() * a.element_size() / sec / 1e9, 1)}
-        del a, b, c
+        # its backward pass: gradients with respect to both operands' log-magnitudes (two more products of the same size)
+        g.lmme(a, b, flags=LMME_FAST, out=c)
+        gc = torch.randn((B, n, n), device=dev, dtype=torch.float32 if name == "c64" else torch.float64)
+        sec = timed(torch, lambda: g.lmme_backward(a, b, c, gc))
+        res[f"lmme_{name}_unit_normal_backward"] = {
+            "ms": round(sec * 1e3, 3), "tflops": round(2 * 2.0 * n ** 3 * B / sec / 1e12, 2),
+            "hbm_gbs": round((3 * a.numel() * a.element_size() + 3 * gc.numel() * gc.element_size()) / sec / 1e9, 1),
+            "kernels_ms": kernel_times(g, lambda: g.lmme_backward(a, b, c, gc))}
+        del a, b, c, gc
         torch.cuda.empty_cache()
     return res
 

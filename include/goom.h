@@ -375,6 +375,24 @@ int goom_to_goom_backward(goom_ctx *ctx, const void *x, const void *grad_re, voi
 int goom_from_goom_backward(goom_ctx *ctx, const void *y, const void *grad_x, void *grad_re, size_t n, int dtype,
                             double eps);
 
+/* Backward of goom_lmme (paper Section 3.2 with the derivatives of Section 3.1 in the limit eps -> 0, as for the
+ * recurrence below).  With C = A B over reals and grad_C[b, i, k] = dL / d Re C'[b, i, k] for some loss L,
+ *     grad_A[b, i, j] = dL / d Re A'[b, i, j] = A_ij sum_k (grad_C_ik / C_ik) B_jk,
+ *     grad_B[b, j, k] = dL / d Re B'[b, j, k] = B_jk sum_i A_ij (grad_C_ik / C_ik),
+ * two products of the same kind, taken over GOOMs by the forward LMME on operands with the row maxima of A' and the
+ * column maxima of B' (as whole numbers) taken out, so that log-magnitudes far from zero lose nothing to the
+ * component type.  An entry of C that is exactly zero passes no gradient, nor does a zero entry of grad_C.
+ * A: [batch, n, d], B: [batch, d, m], C: [batch, n, m] GOOMs as given to and returned by goom_lmme; grad_C:
+ * [batch, n, m], grad_A: [batch, n, d], grad_B: [batch, d, m] reals of the component type (device, caller-owned;
+ * grad_A and grad_B overwritten).  Sizes and flags as for goom_lmme (flags go to both products).  workspace:
+ * goom_lmme_backward_workspace_bytes(...) bytes, required: about (n m + 2 n d + 2 d m) GOOMs per batch item.
+ * Errors: GOOM_EINVAL (null or misaligned pointers, sizes), GOOM_EUNSUPPORTED (sizes beyond goom_lmme's),
+ * GOOM_EWORKSPACE. */
+int goom_lmme_backward(goom_ctx *ctx, const void *A, const void *B, const void *C, const void *grad_C, void *grad_A,
+                       void *grad_B, int64_t batch, int n, int d, int m, int dtype, uint32_t flags, void *workspace,
+                       size_t workspace_bytes);
+size_t goom_lmme_backward_workspace_bytes(int64_t batch, int n, int d, int m, int dtype, uint32_t flags);
+
 /* Backward of goom_affine_scan (time-varying matrices).  grad_H[b, t, i] = dL / d Re H[b, t, i] for some loss L;
  * the call returns dL / d Re A[b, t, i, j], dL / d Re bias[b, t, i] and dL / d Re h0[b, j], as reals of the
  * component type.  The adjoints of the state values, lam_t = grad_H_t / h_t + A_{t+1}^T lam_{t+1}, are a

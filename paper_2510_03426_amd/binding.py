@@ -31,6 +31,7 @@ EXPORTS = [
     "goom_affine_scan", "goom_affine_scan_workspace_bytes", "goom_affine_scan_scaled",
     "goom_affine_scan_scaled_workspace_bytes", "goom_scaled_exp", "goom_log_add_exp",
     "goom_count_nonfinite", "goom_to_goom_backward", "goom_from_goom_backward", "goom_affine_scan_backward", "goom_affine_scan_backward_workspace_bytes",
+    "goom_lmme_backward", "goom_lmme_backward_workspace_bytes",
 ]
 
 
@@ -122,6 +123,9 @@ def load_library():
     lib.goom_affine_scan_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, po, vp, sz]
     lib.goom_affine_scan_backward_workspace_bytes.argtypes = [i64, i32, i64, i32, po]
     lib.goom_affine_scan_backward_workspace_bytes.restype = sz
+    lib.goom_lmme_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, u32, vp, sz]
+    lib.goom_lmme_backward_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, u32]
+    lib.goom_lmme_backward_workspace_bytes.restype = sz
     _lib = lib
     return lib
 
@@ -494,6 +498,26 @@ class Goom:
         self._check(self.lib.goom_affine_scan_backward(self._ctx, _ptr(a), _ptr(bias), _ptr(h0), _ptr(h), _ptr(grad_h), _ptr(ga), _ptr(gb),
                                                        _ptr(gh0), T, d, batch, code, C.byref(opts), _ptr(ws), wsn))
         return ga, gb, gh0
+
+    def lmme_backward(self, a, b, c, grad_c, flags: int = LMME_FAST):
+        """Gradients of a loss with respect to the log-magnitudes of a and b, given c = lmme(a, b) and grad_c = dL / d Re c."""
+        torch = self.torch
+        code = _dtype_code(a)
+        n, d = a.shape[-2:]
+        m = b.shape[-1]
+        lead = a.shape[:-2]
+        batch = 1
+        for s in lead:
+            batch *= s
+        comp = torch.float32 if a.dtype == torch.complex64 else torch.float64
+        assert b.shape == lead + (d, m) and c.shape == lead + (n, m) and grad_c.shape == c.shape
+        assert b.dtype == a.dtype and c.dtype == a.dtype and grad_c.dtype == comp
+        ga = torch.empty(lead + (n, d), dtype=comp, device=a.device)
+        gb = torch.empty(lead + (d, m), dtype=comp, device=a.device)
+        ws, wsn = self.workspace(self.lib.goom_lmme_backward_workspace_bytes(batch, n, d, m, code, flags))
+        self._check(self.lib.goom_lmme_backward(self._ctx, _ptr(a), _ptr(b), _ptr(c), _ptr(grad_c), _ptr(ga), _ptr(gb), batch, n, d, m, code,
+                                                flags, _ptr(ws), wsn))
+        return ga, gb
 
     def scaled_exp(self, z, want_logscale: bool = False):
         """Scaled exponentiation over the last axis: exp(z - max Re z + 2), real."""

@@ -1151,6 +1151,76 @@ int goom_affine_scan_backward(goom_ctx *ctx, const void *A, const void *bias, co
     return launch_affine_backward_gradients(ctx, A, bias, h0, H, mu, grad_A, grad_bias, grad_h0, T, d, batch, dtype);
 }
 
+// Workspace of the LMME backward pass: the shifts, W~', both transposed operands, both products, and what the two
+// forward calls ask for themselves (they run one after the other and share it).
+namespace {
+struct LmmeBackwardPlan {
+    size_t r_bytes, c_bytes, w_bytes, at_bytes, bt_bytes, x_bytes, y_bytes, lmme_bytes;
+    size_t total() const { return r_bytes + c_bytes + w_bytes + at_bytes + bt_bytes + x_bytes + y_bytes + lmme_bytes; }
+};
+LmmeBackwardPlan plan_lmme_backward(int64_t batch, int n, int d, int m, int dtype, uint32_t flags)
+{
+    const size_t rb = comp_bytes(dtype), cb = 2 * rb, bt = (size_t)batch;
+    LmmeBackwardPlan p;
+    p.r_bytes = align_up(bt * n * rb, 256);
+    p.c_bytes = align_up(bt * m * rb, 256);
+    p.w_bytes = align_up(bt * n * m * cb, 256);
+    p.at_bytes = p.x_bytes = align_up(bt * n * d * cb, 256);
+    p.bt_bytes = p.y_bytes = align_up(bt * d * m * cb, 256);
+    const size_t wa = goom_lmme_workspace_bytes(batch, n, m, d, dtype, flags), wb = goom_lmme_workspace_bytes(batch, d, n, m, dtype, flags);
+    p.lmme_bytes = align_up(wa > wb ? wa : wb, 256);
+    return p;
+}
+} // namespace
+
+size_t goom_lmme_backward_workspace_bytes(int64_t batch, int n, int d, int m, int dtype, uint32_t flags)
+{
+    if (batch <= 0 || n <= 0 || d <= 0 || m <= 0 || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
+    if (n > GOOM_MAX_DIM_LMME || d > GOOM_MAX_DIM_LMME || m > GOOM_MAX_DIM_LMME) return 0;
+    return plan_lmme_backward(batch, n, d, m, dtype, flags).total();
+}
+
+int goom_lmme_backward(goom_ctx *ctx, const void *A, const void *B, const void *Cm, const void *grad_C, void *grad_A, void *grad_B, int64_t batch, int n,
+                       int d, int m, int dtype, uint32_t flags, void *ws, size_t ws_bytes)
+{
+    if (int s = check_common(ctx, dtype)) return s;
+    if (flags & ~GOOM_LMME_EXACT) return fail(ctx, GOOM_EINVAL, "unknown LMME flags 0x%x", flags);
+    if (!A || !B || !Cm || !grad_C || !grad_A || !grad_B) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    if (batch <= 0 || n <= 0 || d <= 0 || m <= 0) return fail(ctx, GOOM_EINVAL, "sizes must be positive");
+    if (n > GOOM_MAX_DIM_LMME || d > GOOM_MAX_DIM_LMME || m > GOOM_MAX_DIM_LMME)
+        return fail(ctx, GOOM_EUNSUPPORTED, "n, d, m must be <= %d", GOOM_MAX_DIM_LMME);
+    if ((lmme_is_large(n, m, d) || lmme_is_large(d, n, m)) && batch > 65535)
+        return fail(ctx, GOOM_EUNSUPPORTED, "sizes above %d need batch <= 65535", GOOM_MAX_DIM);
+    const int64_t widest = (int64_t)(n > d ? n : d) * (d > m ? d : m); // one workgroup per 1024 entries of a batch item, or per strip of 32 rows
+    if (batch * ((widest + 1023) / 1024) > 0x7fffffffLL || batch * (((n > m ? n : m) + 31) / 32) > 0x7fffffffLL)
+        return fail(ctx, GOOM_EUNSUPPORTED, "batch too large");
+    if (!aligned(A, 16) || !aligned(B, 16) || !aligned(Cm, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
+    const size_t rb = comp_bytes(dtype);
+    if (!aligned(grad_C, rb) || !aligned(grad_A, rb) || !aligned(grad_B, rb)) return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
+    const LmmeBackwardPlan p = plan_lmme_backward(batch, n, d, m, dtype, flags);
+    if (int s = check_workspace(ctx, ws, ws_bytes, p.total())) return s;
+    if (int s = need_ctx(ctx)) return s;
+    unsigned char *w = static_cast<unsigned char *>(ws);
+    void *r = w;
+    void *c = w + p.r_bytes;
+    void *W = w + p.r_bytes + p.c_bytes;
+    void *At = static_cast<unsigned char *>(W) + p.w_bytes;
+    void *Bt = static_cast<unsigned char *>(At) + p.at_bytes;
+    void *X = static_cast<unsigned char *>(Bt) + p.bt_bytes;
+    void *Y = static_cast<unsigned char *>(X) + p.x_bytes;
+    void *lw = p.lmme_bytes ? static_cast<unsigned char *>(Y) + p.y_bytes : nullptr;
+    // shifts, W~' = GOOM(G) - C~', and the shifted operands transposed ...
+    if (int s = launch_lmme_backward_prepare(ctx, A, B, Cm, grad_C, r, c, W, At, Bt, batch, n, d, m, dtype)) return s;
+    // ... X~ = W~ B~^T [n, d] and Y~ = A~^T W~ [d, m], by the forward product itself ...
+    ctx->prof_keep = true;
+    int st = goom_lmme(ctx, W, Bt, X, batch, n, m, d, dtype, flags, lw, p.lmme_bytes);
+    if (!st) st = goom_lmme(ctx, At, W, Y, batch, d, n, m, dtype, flags, lw, p.lmme_bytes);
+    ctx->prof_keep = false;
+    if (st) return st;
+    // ... and the gradients A~ . X~, B~ . Y~ as reals
+    return launch_lmme_backward_finish(ctx, A, B, X, Y, r, c, grad_A, grad_B, batch, n, d, m, dtype);
+}
+
 int goom_to_goom_backward(goom_ctx *ctx, const void *x, const void *grad_re, void *grad_x, size_t n, int dtype, double eps)
 {
     if (int s = check_common(ctx, dtype)) return s;

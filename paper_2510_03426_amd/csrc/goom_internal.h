@@ -166,6 +166,11 @@ int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, 
                                    long long batch, int dtype);
 int launch_affine_backward_gradients(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
                                      void *gb, void *gh0, long long T, int d, long long batch, int dtype);
+// backward of LMME (goom_lmme_backward.hip): shifts r [batch, n], c [batch, m]; W [batch, n, m], At [batch, d, n], Bt [batch, m, d] GOOMs
+int launch_lmme_backward_prepare(goom_ctx *ctx, const void *A, const void *B, const void *Cm, const void *G, void *r, void *c, void *W, void *At, void *Bt,
+                                 long long batch, int n, int d, int m, int dtype);
+int launch_lmme_backward_finish(goom_ctx *ctx, const void *A, const void *B, const void *X, const void *Y, const void *r, const void *c, void *gA, void *gB,
+                                long long batch, int n, int d, int m, int dtype);
 int launch_widen_goom(goom_ctx *ctx, const void *z64, void *z128, size_t n); // complex64 GOOMs -> complex128 GOOMs
 int launch_count_nonfinite(goom_ctx *ctx, const void *z, size_t n, int dtype, unsigned long long *count);
 int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t nvec, int d, int dtype);

@@ -884,6 +884,54 @@ def test_affine_scan_backward(G, oracle, T, d, batch, chunk, ctype, with_h0, gai
         assert np.all(ga[:, 0] == 0)  # the first matrix multiplies a zero vector
 
 
+@pytest.mark.parametrize("shape,ctype,flags,spread", [
+    ((3, 16, 16, 16), np.complex64, 0, 0.0), ((2, 37, 50, 29), np.complex64, 0, 4000.0), ((2, 128, 128, 128), np.complex64, 0, 300.0),
+    ((2, 128, 128, 128), np.complex64, 1, 4000.0), ((1, 200, 130, 70), np.complex64, 0, 4000.0), ((5, 8, 64, 1), np.complex64, 0, 100.0),
+    ((2, 1, 1, 1), np.complex64, 0, 50.0), ((2, 40, 24, 56), np.complex128, 0, 4000.0), ((1, 128, 128, 128), np.complex128, 0, 1e5),
+    ((2, 64, 32, 100), np.complex64, 1, 1000.0), ((1, 70, 150, 40), np.complex128, 0, 500.0)])
+def test_lmme_backward(G, oracle, shape, ctype, flags, spread):
+    """Gradients of a loss with respect to the log-magnitudes of both operands of an LMME, against the oracle fed the
+    same forward result.  Every gradient is a signed sum of terms G_ik A_ij B_jk / C_ik; the bound is on the error
+    relative to the sum of their magnitudes (the oracle's own sums on operands with all signs positive), which is what
+    a product in the component type can hold."""
+    comp = np.float32 if ctype == np.complex64 else np.float64
+    b, n, d, m = shape
+    rng = np.random.default_rng(17)
+    say(f"lmme backward batch={b} n={n} d={d} m={m} {np.dtype(ctype).name} flags={flags} spread={spread}")
+    A = oracle.to_goom(si.normal_f32(si.BASE_SEED + 95, 7, b * n * d).reshape(b, n, d).astype(comp))
+    B = oracle.to_goom(si.normal_f32(si.BASE_SEED + 96, 8, b * d * m).reshape(b, d, m).astype(comp))
+    A.real += rng.uniform(-spread, spread, (b, n, 1)).astype(comp)  # rows and columns far outside float range
+    B.real += rng.uniform(-spread, spread, (b, 1, m)).astype(comp)
+    Gc = si.normal_f32(si.BASE_SEED + 97, 10, b * n * m).reshape(b, n, m).astype(comp)
+    if n * d > 8:
+        A[0, 0, 1] = -np.inf      # a zero entry
+        Gc[0, n - 1, 0] = 0.0     # an output the loss does not see
+    Cd = G.lmme(dev(A), dev(B), flags=flags)
+    Cz = host(Cd)
+    if n > 2 and m > 2:
+        Cz[b - 1, 1, 2] = -np.inf  # an output taken to be exactly zero passes no gradient
+        Cd = dev(Cz)
+    ga, gb = G.lmme_backward(dev(A), dev(B), Cd, dev(Gc), flags=flags)
+    ga, gb = host(ga).astype(np.float64), host(gb).astype(np.float64)
+    wa, wb = oracle.lmme_backward(A, B, Gc, c=Cz)
+    ma, mb = oracle.lmme_backward(A.real + 0j, B.real + 0j, np.abs(Gc), c=Cz.real + 0j)  # sums of the terms' magnitudes
+    assert np.all(ma >= np.abs(wa) * (1 - 1e-12)) and np.all(mb >= np.abs(wb) * (1 - 1e-12))
+    rel = 1e-5 if comp == np.float32 else 1e-11
+    tiny = 2 * float(np.finfo(comp).tiny)  # (results are reals of the component type; subnormal ones may be flushed)
+    ea, eb = np.abs(ga - wa) / (rel * ma + tiny), np.abs(gb - wb) / (rel * mb + tiny)
+    say(f"  worst error / tolerance: grad A {ea.max():.3g}, grad B {eb.max():.3g}; largest |grad| {np.abs(wa).max():.3g}")
+    assert np.isfinite(ga).all() and np.isfinite(gb).all()
+    assert ea.max() <= 1 and eb.max() <= 1
+    sig_a, sig_b = np.abs(wa) > 2 * (rel * ma + tiny), np.abs(wb) > 2 * (rel * mb + tiny)
+    assert np.array_equal(np.signbit(ga)[sig_a], np.signbit(wa)[sig_a]) and np.array_equal(np.signbit(gb)[sig_b], np.signbit(wb)[sig_b])
+    if n * d > 8:
+        assert ga[0, 0, 1] == 0.0
+    # the sum rules, on the device results alone: the gradients of row i of A' add up to those of row i of C' that pass
+    live = np.where(np.isneginf(Cz.real), 0.0, Gc.astype(np.float64))
+    assert np.all(np.abs(ga.sum(axis=2) - live.sum(axis=2)) <= 4 * rel * ma.sum(axis=2) + 1e-30)
+    assert np.all(np.abs(gb.sum(axis=1) - live.sum(axis=1)) <= 4 * rel * mb.sum(axis=1) + 1e-30)
+
+
 @pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
 def test_signed_log_add(G, oracle, ctype):
     comp = np.float32 if ctype == np.complex64 else np.float64
