@@ -996,3 +996,93 @@ ORACLE_API void oracle_lmme_backward(const double *are, const uint8_t *asg, cons
     free(z);
     free(s);
 }
+
+/* Backward pass of the prefix scan P_t = M_t P_{t-1} over GOOMs (Section 4.1; derivatives of Section 3.1 in the
+ * limit eps -> 0, as above).  P_{-1} is the initial state S0 (d x m) or, without one, the identity (m = d, so that
+ * P_0 = M_0).  Given G_t[i, k] = dL / d Re P'_t[i, k], the adjoints of the values are d x m matrices that run
+ * backwards through the transposed factors,
+ *     Lam_t = G_t / P_t (entry by entry) + M_{t+1}^T Lam_{t+1},        Lam_{T-1} = G_{T-1} / P_{T-1},
+ * and with d v / d log|v| = v
+ *     dL / d Re M'_t[i, j] = M_t[i, j] sum_k Lam_t[i, k] P_{t-1}[j, k],
+ *     dL / d Re S0'[j, k] = S0[j, k] sum_i M_0[i, j] Lam_0[i, k].
+ * An entry of a state that is exactly zero passes no gradient.  M [T, d, d], S0 [d, m] or NULL, P [T, d, m] the
+ * forward states, G [T, d, m] reals.  Outputs: gM [T, d, d], gS0 [d, m] or NULL, the adjoints as GOOMs lam [T, d, m]. */
+ORACLE_API void oracle_scan_backward(const double *mre, const uint8_t *msg, const double *s0re, const uint8_t *s0sg,
+                                     const double *pre, const uint8_t *psg, const double *G, double *gM, double *gS0,
+                                     double *lre, uint8_t *lsg, long T, int d, int m)
+{
+    const size_t dd = (size_t)d * d, dm = (size_t)d * m;
+    const int len = (d > m ? d : m) + 1;
+    double *z = (double *)malloc(sizeof(double) * (size_t)len);
+    uint8_t *s = (uint8_t *)malloc((size_t)len);
+    for (long t = T - 1; t >= 0; --t)
+        for (int i = 0; i < d; ++i)
+            for (int k = 0; k < m; ++k) {
+                int n = 0;
+                const size_t e = (size_t)t * dm + (size_t)i * m + k;
+                if (G[e] != 0.0 && pre[e] > -INFINITY) {
+                    z[n] = log(fabs(G[e])) - pre[e];
+                    s[n] = (uint8_t)((G[e] < 0.0) ^ psg[e]);
+                    ++n;
+                }
+                if (t + 1 < T)
+                    for (int j = 0; j < d; ++j) { /* (M_{t+1}^T Lam_{t+1})[i, k] = sum_j M_{t+1}[j, i] Lam_{t+1}[j, k] */
+                        const double a = mre[(size_t)(t + 1) * dd + (size_t)j * d + i], l = lre[(size_t)(t + 1) * dm + (size_t)j * m + k];
+                        if (a == -INFINITY || l == -INFINITY) continue;
+                        z[n] = a + l;
+                        s[n] = msg[(size_t)(t + 1) * dd + (size_t)j * d + i] ^ lsg[(size_t)(t + 1) * dm + (size_t)j * m + k];
+                        ++n;
+                    }
+                signed_lse(n, z, s, &lre[e], &lsg[e], NULL);
+            }
+    for (long t = 0; t < T; ++t)
+        for (int i = 0; i < d; ++i)
+            for (int j = 0; j < d; ++j) {
+                const double a = mre[(size_t)t * dd + (size_t)i * d + j];
+                int n = 0;
+                for (int k = 0; k < m; ++k) {
+                    double pr;
+                    uint8_t ps;
+                    if (t > 0) {
+                        pr = pre[(size_t)(t - 1) * dm + (size_t)j * m + k];
+                        ps = psg[(size_t)(t - 1) * dm + (size_t)j * m + k];
+                    } else if (s0re) {
+                        pr = s0re[(size_t)j * m + k];
+                        ps = s0sg[(size_t)j * m + k];
+                    } else {
+                        pr = j == k ? 0.0 : -INFINITY; /* the identity */
+                        ps = 0;
+                    }
+                    const double l = lre[(size_t)t * dm + (size_t)i * m + k];
+                    if (pr == -INFINITY || l == -INFINITY || a == -INFINITY) continue;
+                    z[n] = (double)((long double)a + (long double)l + (long double)pr);
+                    s[n] = (uint8_t)(msg[(size_t)t * dd + (size_t)i * d + j] ^ lsg[(size_t)t * dm + (size_t)i * m + k] ^ ps);
+                    ++n;
+                }
+                double re;
+                uint8_t sg;
+                signed_lse(n, z, s, &re, &sg, NULL);
+                const double v = re > -INFINITY ? (double)expl((long double)re) : 0.0;
+                gM[(size_t)t * dd + (size_t)i * d + j] = sg ? -v : v;
+            }
+    if (gS0)
+        for (int j = 0; j < d; ++j)
+            for (int k = 0; k < m; ++k) {
+                int n = 0;
+                const double sr = s0re ? s0re[(size_t)j * m + k] : -INFINITY;
+                for (int i = 0; i < d && sr > -INFINITY; ++i) {
+                    const double a = mre[(size_t)i * d + j], l = lre[(size_t)i * m + k];
+                    if (a == -INFINITY || l == -INFINITY) continue;
+                    z[n] = (double)((long double)sr + (long double)a + (long double)l);
+                    s[n] = (uint8_t)(s0sg[(size_t)j * m + k] ^ msg[(size_t)i * d + j] ^ lsg[(size_t)i * m + k]);
+                    ++n;
+                }
+                double re;
+                uint8_t sg;
+                signed_lse(n, z, s, &re, &sg, NULL);
+                const double v = re > -INFINITY ? (double)expl((long double)re) : 0.0;
+                gS0[(size_t)j * m + k] = sg ? -v : v;
+            }
+    free(z);
+    free(s);
+}

@@ -261,6 +261,28 @@ def affine_scan_backward(a, b, grad_h, h0=None, h=None):
     return gA, gb, gh0, (lre, lsg)
 
 
+def scan_backward(mats, grad_p, init=None, p=None):
+    """Backward pass of the prefix scan P_t = M_t P_{t-1} over GOOMs (Sections 3.1, 4.1): given grad_p[t, i, k] =
+    dL / d Re P'_t[i, k], returns (dL / d Re M' [T, d, d], dL / d Re init' [d, m] or None, adjoints as (re, sg)).
+    mats: [T, d, d]; init: [d, m] or None (the identity); p: the forward states to use (default: computed here)."""
+    mre, msg = _as_working(mats)
+    T, d, _ = mre.shape
+    if init is not None:
+        ire, isg = _as_working(init)
+        m = ire.shape[1]
+    else:
+        ire = isg = None
+        m = d
+    pre, psg = scan(mats, init) if p is None else _as_working(p)
+    G = _c(grad_p, np.float64)
+    assert G.shape == (T, d, m) and pre.shape == (T, d, m)
+    gM = np.empty((T, d, d)); gI = np.empty((d, m)) if init is not None else None
+    lre = np.empty((T, d, m)); lsg = np.empty((T, d, m), dtype=np.uint8)
+    lib().oracle_scan_backward(_p(mre), _p(msg), _p(ire), _p(isg), _p(pre), _p(psg), _p(G), _p(gM), _p(gI), _p(lre), _p(lsg),
+                               C.c_long(T), C.c_int(d), C.c_int(m))
+    return gM, gI, (lre, lsg)
+
+
 def lmme_backward(a, b, grad_c, c=None):
     """Backward pass of C' = LMME(A', B') (Sections 3.1, 3.2): given grad_c[..., i, k] = dL / d Re C'_ik, returns
     (dL / d Re A', dL / d Re B') as reals.  a: [..., n, d], b: [..., d, m]; c: the forward result to use (default:

@@ -188,3 +188,80 @@ def test_lmme_backward_sum_rules_and_special_cases(oracle):
     gAb, gBb = oracle.lmme_backward(Ab, Bb, Gb)
     gAq, gBq = oracle.lmme_backward(Ab[1, 2], Bb[1, 2], Gb[1, 2])
     assert np.array_equal(gAb[1, 2], gAq) and np.array_equal(gBb[1, 2], gBq)
+
+
+def scan_loss_value_domain(M, S0, G):
+    """L = sum_t sum_ik G[t, i, k] log|P_t[i, k]| with P_t = M_t P_{t-1}, P_{-1} = S0 (the identity if None), in long double."""
+    P = np.eye(M.shape[1], dtype=np.longdouble) if S0 is None else S0.astype(np.longdouble)
+    L = np.longdouble(0)
+    for t in range(M.shape[0]):
+        P = (M[t].astype(np.longdouble)[:, :, None] * P[None, :, :]).sum(axis=1)
+        L += (G[t].astype(np.longdouble) * np.log(np.abs(P))).sum()
+    return L
+
+
+def test_scan_backward_against_finite_differences(oracle):
+    rng = np.random.default_rng(51)
+    T, d, m = 7, 4, 3
+    M = rng.standard_normal((T, d, d)) * 0.9
+    S0 = rng.standard_normal((d, m))
+    G = rng.standard_normal((T, d, m))
+    delta = 1e-5
+    for init in (S0, None):
+        Gi = G if init is not None else rng.standard_normal((T, d, d))
+        gM, gI, _ = oracle.scan_backward(goom_of(M), Gi, init=None if init is None else goom_of(init))
+        for (t, i, j) in [(0, 0, 0), (0, 2, 3), (3, 1, 2), (6, 3, 3), (5, 2, 0), (1, 3, 1), (6, 0, 2)]:
+            Mp, Mm = M.copy(), M.copy()
+            Mp[t, i, j] *= math.exp(delta)
+            Mm[t, i, j] *= math.exp(-delta)
+            fd = float((scan_loss_value_domain(Mp, init, Gi) - scan_loss_value_domain(Mm, init, Gi)) / (2 * delta))
+            assert abs(gM[t, i, j] - fd) < 1e-7 * max(1.0, abs(fd)), (t, i, j, gM[t, i, j], fd)
+        if init is None:
+            assert gI is None
+            continue
+        for (j, k) in [(0, 0), (3, 2), (1, 1), (2, 0)]:
+            Sp, Sm = S0.copy(), S0.copy()
+            Sp[j, k] *= math.exp(delta)
+            Sm[j, k] *= math.exp(-delta)
+            fd = float((scan_loss_value_domain(M, Sp, G) - scan_loss_value_domain(M, Sm, G)) / (2 * delta))
+            assert abs(gI[j, k] - fd) < 1e-7 * max(1.0, abs(fd)), (j, k, gI[j, k], fd)
+
+
+def test_scan_backward_sum_rules_and_special_cases(oracle):
+    rng = np.random.default_rng(52)
+    T, d, m = 60, 5, 3
+    M = goom_of(rng.standard_normal((T, d, d))) + 25.0   # every entry times e^25: states of magnitude e^(25 t)
+    S0 = goom_of(rng.standard_normal((d, m)))
+    G = rng.standard_normal((T, d, m))
+    gM, gI, (lre, lsg) = oracle.scan_backward(M, G, init=S0)
+    pre, psg = oracle.scan(M, S0)
+    assert pre.max() > 1400 and lre.min() < -1400 and np.isfinite(gM).all() and np.abs(gM).max() < 1e7
+    # scaling row i of M_t by e^s scales row i of P_t and, through the later factors, every later state:
+    # sum_j gM_t[i, j] = sum_k (adjoint times state)_t[i, k]; at the last step that is sum_k G[i, k]
+    lam_p = np.where(lsg ^ psg, -1.0, 1.0) * np.exp(lre + pre)
+    assert np.allclose(gM.sum(axis=2), lam_p.sum(axis=2), rtol=1e-8, atol=1e-10)
+    assert np.allclose(gM[-1].sum(axis=1), G[-1].sum(axis=1), rtol=1e-9, atol=1e-11)
+    # scaling the whole of M_t by e^s adds s to every log-magnitude of P_u, u >= t: the gradients of M_t add up to sum_{u >= t} sum G_u
+    tail = np.cumsum(G.sum(axis=(1, 2))[::-1])[::-1]
+    assert np.allclose(gM.sum(axis=(1, 2)), tail, rtol=1e-7, atol=1e-9)
+    # scaling column k of S0 scales column k of every state; scaling row j of S0 by e^s and column j of M_0 by e^-s changes nothing
+    assert np.allclose(gI.sum(axis=0), G.sum(axis=(0, 1)), rtol=1e-7, atol=1e-9)
+    assert np.allclose(gI.sum(axis=1), gM[0].sum(axis=0), rtol=1e-7, atol=1e-9)
+    # between neighbouring factors: scaling column j of M_{t+1} by e^-s and row j of M_t by e^s changes only row j of P_t
+    assert np.allclose(gM[1:].sum(axis=1), gM[:-1].sum(axis=2) - G[:-1].sum(axis=2), rtol=1e-7, atol=1e-9)
+    # a common shift of all log-magnitudes changes no gradient
+    gM2, gI2, _ = oracle.scan_backward(M + 3.0, G, init=S0 - 7.0)
+    assert np.allclose(gM2, gM, rtol=1e-7, atol=1e-9) and np.allclose(gI2, gI, rtol=1e-7, atol=1e-9)
+    # one step is an LMME: the same gradients as its backward pass
+    gM1, gI1, _ = oracle.scan_backward(M[:1], G[:1], init=S0)
+    gA, gB = oracle.lmme_backward(M[0], S0, G[0])
+    assert np.allclose(gM1[0], gA, rtol=1e-12) and np.allclose(gI1, gB, rtol=1e-12)
+    # scalars, no initial state: P_t = a_0 ... a_t, dL / d log a_s = sum_{t >= s} G_t
+    a = goom_of(np.array([1.5, -0.5, 2.0, -3.0]).reshape(4, 1, 1))
+    Gs = np.array([1.0, 10.0, 100.0, 1000.0]).reshape(4, 1, 1)
+    g1, none, _ = oracle.scan_backward(a, Gs)
+    assert none is None and np.allclose(g1[:, 0, 0], [1111.0, 1110.0, 1100.0, 1000.0])
+    # diagonal factors, no initial state: every state is diagonal, off-diagonal entries are zero and pass nothing
+    D = np.zeros((3, 2, 2)); D[:, 0, 0] = [2.0, 3.0, 4.0]; D[:, 1, 1] = [-1.0, 5.0, 0.5]
+    gD, _, _ = oracle.scan_backward(goom_of(D), np.ones((3, 2, 2)))
+    assert np.allclose(gD[:, 0, 0], [3, 2, 1]) and np.allclose(gD[:, 1, 1], [3, 2, 1]) and np.all(gD[:, 0, 1] == 0) and np.all(gD[:, 1, 0] == 0)
