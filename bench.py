@@ -34,7 +34,7 @@ def main():
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (default: looked up in "
                          "the counter summaries under profiles/ for this kernel and workload, null when there is none)")
     ap.add_argument("--no-extras", action="store_true", help="time the headline scan only")
-    ap.add_argument("--only", choices=["tiny", "between", "scan128", "complex128", "lmme", "lyapunov", "recurrence", "large"], default=None,
+    ap.add_argument("--only", choices=["tiny", "between", "scan128", "complex128", "lmme", "lyapunov", "recurrence", "large", "backward"], default=None,
                     help="time just one of the other workloads (for profiler runs) and print its figures")
     ap.add_argument("--basic-extras", action="store_true",
                     help="besides the scan, time only a plain device copy of the same size (for counter runs)")
@@ -306,6 +306,27 @@ def other_workloads(g, torch, dev, only=None):
         res.update(recurrence(g, torch, dev, si))
     if want("large"):
         res.update(large_matrices(g, torch, dev, si))
+    if want("backward"):
+        res.update(scan_backward(g, torch, dev, si))
+    return res
+
+
+def scan_backward(g, torch, dev, si):
+    # backward pass of a scan of 64 x 64 matrices, T = 65,536: gradients with respect to every factor's log-magnitudes
+    res = {}
+    T, d = 1 << 16, 64
+    z = torch.empty((T, d, d), dtype=torch.complex64, device=dev)
+    for t0, x in si.device_normal_blocks(251003426 * 10 + 6, T, (d, d), dev, 1 << 14):
+        g.to_goom(x, out=z[t0:t0 + x.shape[0]])
+    p = g.scan(z)
+    gp = torch.randn((T, d, d), device=dev, generator=si.device_generator(251003426 * 10 + 7, dev))
+    fwd = timed(torch, lambda: g.scan(z, out=p))
+    sec = timed(torch, lambda: g.scan_backward(z, p, gp))
+    res["scan_backward_T65536_d64"] = {
+        "ms": round(sec * 1e3, 3), "forward_ms": round(fwd * 1e3, 3), "products_per_s": round(T / sec, 1),
+        "kernels_ms": kernel_times(g, lambda: g.scan_backward(z, p, gp))}
+    del z, p, gp
+    torch.cuda.empty_cache()
     return res
 
 

@@ -393,6 +393,25 @@ int goom_lmme_backward(goom_ctx *ctx, const void *A, const void *B, const void *
                        size_t workspace_bytes);
 size_t goom_lmme_backward_workspace_bytes(int64_t batch, int n, int d, int m, int dtype, uint32_t flags);
 
+/* Backward of goom_scan (paper Section 4.1 with the derivatives of Section 3.1 in the limit eps -> 0).  With
+ * P_t = M_t P_{t-1}, P_{-1} = S0 (the identity without one), and grad_P[b, t, i, k] = dL / d Re P[b, t, i, k],
+ * the adjoints of the state values, Lam_t = grad_P_t / P_t + M_{t+1}^T Lam_{t+1} (d x m matrices), are the upper
+ * block of a prefix scan of stacked (d + m) x (d + m) matrices [[M_{t+1}^T, grad_P_t / P_t], [0, I]] in reverse
+ * time, run by goom_scan itself on log-magnitudes shifted to ordinary size, and
+ *     grad_M[b, t, i, j] = M_t[i, j] sum_k Lam_t[i, k] P_{t-1}[j, k],    grad_S0[b, j, k] = S0[j, k] (M_0^T Lam_0)[j, k]
+ * (one batched LMME).  A state entry that is exactly zero passes no gradient.
+ * M: [batch, T, d, d], S0: NULL or [batch, d, m], P: [batch, T, d, m] GOOMs as given to and returned by goom_scan
+ * (m = d without S0); grad_P: [batch, T, d, m], grad_M: [batch, T, d, d], grad_S0: NULL or [batch, d, m] (needs
+ * S0) reals of the component type; device, caller-owned, outputs overwritten.  d + m <= GOOM_MAX_DIM_LMME.
+ * opts: as for goom_scan (chunk length of the reverse scan); flags must be 0.  workspace:
+ * goom_scan_backward_workspace_bytes(..., with_init = S0 != NULL) bytes, required: about
+ * (d + m)(d + 2 m) GOOMs per step.  Errors: GOOM_EINVAL, GOOM_EUNSUPPORTED (sizes), GOOM_EWORKSPACE. */
+int goom_scan_backward(goom_ctx *ctx, const void *M, const void *S0, const void *P, const void *grad_P, void *grad_M,
+                       void *grad_S0, int64_t T, int d, int m, int64_t batch, int dtype, const goom_scan_opts *opts,
+                       void *workspace, size_t workspace_bytes);
+size_t goom_scan_backward_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype,
+                                          const goom_scan_opts *opts, int with_init);
+
 /* Backward of goom_affine_scan (time-varying matrices).  grad_H[b, t, i] = dL / d Re H[b, t, i] for some loss L;
  * the call returns dL / d Re A[b, t, i, j], dL / d Re bias[b, t, i] and dL / d Re h0[b, j], as reals of the
  * component type.  The adjoints of the state values, lam_t = grad_H_t / h_t + A_{t+1}^T lam_{t+1}, are a

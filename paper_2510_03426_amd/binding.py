@@ -31,7 +31,7 @@ EXPORTS = [
     "goom_affine_scan", "goom_affine_scan_workspace_bytes", "goom_affine_scan_scaled",
     "goom_affine_scan_scaled_workspace_bytes", "goom_scaled_exp", "goom_log_add_exp",
     "goom_count_nonfinite", "goom_to_goom_backward", "goom_from_goom_backward", "goom_affine_scan_backward", "goom_affine_scan_backward_workspace_bytes",
-    "goom_lmme_backward", "goom_lmme_backward_workspace_bytes",
+    "goom_lmme_backward", "goom_lmme_backward_workspace_bytes", "goom_scan_backward", "goom_scan_backward_workspace_bytes",
 ]
 
 
@@ -126,6 +126,9 @@ def load_library():
     lib.goom_lmme_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, u32, vp, sz]
     lib.goom_lmme_backward_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, u32]
     lib.goom_lmme_backward_workspace_bytes.restype = sz
+    lib.goom_scan_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i64, i32, po, vp, sz]
+    lib.goom_scan_backward_workspace_bytes.argtypes = [i64, i32, i32, i64, i32, po, i32]
+    lib.goom_scan_backward_workspace_bytes.restype = sz
     _lib = lib
     return lib
 
@@ -518,6 +521,22 @@ class Goom:
         self._check(self.lib.goom_lmme_backward(self._ctx, _ptr(a), _ptr(b), _ptr(c), _ptr(grad_c), _ptr(ga), _ptr(gb), batch, n, d, m, code,
                                                 flags, _ptr(ws), wsn))
         return ga, gb
+
+    def scan_backward(self, mats, p, grad_p, init=None, chunk_len: int = 0):
+        """Gradients of a loss with respect to the log-magnitudes of the factors (and of init), given the scan's states p and
+        grad_p = dL / d Re p."""
+        torch = self.torch
+        code = _dtype_code(mats)
+        lead, batch, T, d, m = self._scan_shapes(mats, init)
+        comp = torch.float32 if mats.dtype == torch.complex64 else torch.float64
+        assert p.shape == lead + (T, d, m) and grad_p.shape == p.shape and p.dtype == mats.dtype and grad_p.dtype == comp
+        opts = ScanOpts(chunk_len, 0)
+        gm = torch.empty(lead + (T, d, d), dtype=comp, device=mats.device)
+        gi = torch.empty(lead + (d, m), dtype=comp, device=mats.device) if init is not None else None
+        ws, wsn = self.workspace(self.lib.goom_scan_backward_workspace_bytes(T, d, m, batch, code, C.byref(opts), int(init is not None)))
+        self._check(self.lib.goom_scan_backward(self._ctx, _ptr(mats), _ptr(init), _ptr(p), _ptr(grad_p), _ptr(gm), _ptr(gi), T, d, m, batch, code,
+                                                C.byref(opts), _ptr(ws), wsn))
+        return gm, gi
 
     def scaled_exp(self, z, want_logscale: bool = False):
         """Scaled exponentiation over the last axis: exp(z - max Re z + 2), real."""

@@ -1221,6 +1221,88 @@ int goom_lmme_backward(goom_ctx *ctx, const void *A, const void *B, const void *
     return launch_lmme_backward_finish(ctx, A, B, X, Y, r, c, grad_A, grad_B, batch, n, d, m, dtype);
 }
 
+// Workspace of the scan's backward pass.  The stacked factors are dead once the reverse scan has run: the operands
+// and the result of the gradient products lie in their place ((d + m)^2 >= 2 d m + d^2 entries per step).
+namespace {
+struct ScanBackwardPlan {
+    size_t c_bytes, f_bytes, init_bytes, states_bytes, scan_bytes, lmme_bytes;
+    size_t lam_off, pt_off, x_off; // inside the factors' region
+    int64_t lmme_slice;            // (b, t) pairs per LMME call
+    size_t total() const { return c_bytes + f_bytes + init_bytes + states_bytes + scan_bytes + lmme_bytes; }
+};
+ScanBackwardPlan plan_scan_backward(int64_t T, int d, int m, int64_t batch, int dtype, const goom_scan_opts *opts, bool with_init)
+{
+    const size_t rb = comp_bytes(dtype), cb = 2 * rb, bt = (size_t)batch;
+    const int D = d + m;
+    const int64_t nsteps = T + (with_init ? 1 : 0);
+    ScanBackwardPlan p;
+    p.c_bytes = align_up(bt * (size_t)(T + 1) * rb, 256);
+    p.f_bytes = align_up(bt * (size_t)nsteps * D * D * cb, 256) + 512;
+    p.init_bytes = align_up(bt * D * m * cb, 256);
+    p.states_bytes = align_up(bt * (size_t)nsteps * D * m * cb, 256);
+    p.scan_bytes = align_up(goom_scan_workspace_bytes(nsteps, D, m, batch, dtype, opts), 256);
+    p.lam_off = 0;
+    p.pt_off = align_up(bt * (size_t)T * d * m * cb, 256);
+    p.x_off = p.pt_off + align_up(bt * (size_t)T * m * d * cb, 256);
+    // above 128 the product takes at most 65535 pairs per call
+    const bool large = d > GOOM_MAX_DIM || m > GOOM_MAX_DIM;
+    p.lmme_slice = large && batch * T > 65535 ? 65535 : batch * T;
+    p.lmme_bytes = align_up(goom_lmme_workspace_bytes(p.lmme_slice, d, m, d, dtype, 0), 256);
+    return p;
+}
+} // namespace
+
+size_t goom_scan_backward_workspace_bytes(int64_t T, int d, int m, int64_t batch, int dtype, const goom_scan_opts *opts, int with_init)
+{
+    if (T <= 0 || d <= 0 || m <= 0 || batch <= 0 || d + m > GOOM_MAX_DIM_LMME) return 0;
+    if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
+    if (!with_init && m != d) return 0;
+    return plan_scan_backward(T, d, m, batch, dtype, opts, with_init != 0).total();
+}
+
+int goom_scan_backward(goom_ctx *ctx, const void *M, const void *S0, const void *P, const void *grad_P, void *grad_M, void *grad_S0, int64_t T, int d, int m,
+                       int64_t batch, int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes)
+{
+    if (int s = check_scan_args(ctx, M, P, T, d, m, batch, dtype, opts, GOOM_MAX_DIM_LMME)) return s;
+    if (!grad_P || !grad_M) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    if (!S0 && m != d) return fail(ctx, GOOM_EINVAL, "without an initial state the states are d x d (d=%d m=%d)", d, m);
+    if (grad_S0 && !S0) return fail(ctx, GOOM_EINVAL, "a gradient for the initial state needs the initial state");
+    if (d + m > GOOM_MAX_DIM_LMME) return fail(ctx, GOOM_EUNSUPPORTED, "the backward pass needs d + m <= %d (d=%d m=%d)", GOOM_MAX_DIM_LMME, d, m);
+    if (batch * (T + 1) > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "batch * T too large");
+    if (S0 && !aligned(S0, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
+    const size_t rb = comp_bytes(dtype);
+    if (!aligned(grad_P, rb) || !aligned(grad_M, rb) || (grad_S0 && !aligned(grad_S0, rb))) return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
+    const ScanBackwardPlan p = plan_scan_backward(T, d, m, batch, dtype, opts, S0 != nullptr);
+    if (int s = check_workspace(ctx, ws, ws_bytes, p.total())) return s;
+    if (int s = need_ctx(ctx)) return s;
+    unsigned char *w = static_cast<unsigned char *>(ws);
+    void *c = w;
+    unsigned char *F = w + p.c_bytes;
+    void *init = F + p.f_bytes;
+    void *states = static_cast<unsigned char *>(init) + p.init_bytes;
+    void *scan_ws = p.scan_bytes ? static_cast<unsigned char *>(states) + p.states_bytes : nullptr;
+    void *lmme_ws = p.lmme_bytes ? static_cast<unsigned char *>(states) + p.states_bytes + p.scan_bytes : nullptr;
+    const int64_t nsteps = T + (S0 ? 1 : 0);
+    // scales of the states, the stacked factors [[e^(c_t - c_{t+1}) M_{t+1}^T, G_t / (P_t e^(-c_t))], [0, I]] in reverse time ...
+    if (int s = launch_scan_backward_prepare(ctx, M, S0, P, grad_P, c, F, init, T, d, m, batch, dtype)) return s;
+    // ... the adjoints on top of an identity, by the forward scan itself ...
+    ctx->prof_keep = true;
+    int st = goom_scan(ctx, F, init, states, nsteps, d + m, m, batch, dtype, opts, scan_ws, p.scan_bytes);
+    // ... one product per step, adjoint times the transposed previous state ...
+    void *Lam = F + p.lam_off, *Pt = F + p.pt_off, *X = F + p.x_off;
+    if (!st) st = launch_scan_backward_operands(ctx, states, P, S0, c, Lam, Pt, T, d, m, batch, dtype);
+    const size_t cb = 2 * rb;
+    for (int64_t at = 0; !st && at < batch * T; at += p.lmme_slice) {
+        const int64_t count = batch * T - at < p.lmme_slice ? batch * T - at : p.lmme_slice;
+        st = goom_lmme(ctx, static_cast<unsigned char *>(Lam) + (size_t)at * d * m * cb, static_cast<unsigned char *>(Pt) + (size_t)at * m * d * cb,
+                       static_cast<unsigned char *>(X) + (size_t)at * d * d * cb, count, d, m, d, dtype, GOOM_LMME_FAST, lmme_ws, p.lmme_bytes);
+    }
+    ctx->prof_keep = false;
+    if (st) return st;
+    // ... and the gradients as reals
+    return launch_scan_backward_gradients(ctx, M, S0, X, states, c, grad_M, grad_S0, T, d, m, batch, dtype);
+}
+
 int goom_to_goom_backward(goom_ctx *ctx, const void *x, const void *grad_re, void *grad_x, size_t n, int dtype, double eps)
 {
     if (int s = check_common(ctx, dtype)) return s;

@@ -171,6 +171,14 @@ int launch_lmme_backward_prepare(goom_ctx *ctx, const void *A, const void *B, co
                                  long long batch, int n, int d, int m, int dtype);
 int launch_lmme_backward_finish(goom_ctx *ctx, const void *A, const void *B, const void *X, const void *Y, const void *r, const void *c, void *gA, void *gB,
                                 long long batch, int n, int d, int m, int dtype);
+// backward of the prefix scan (goom_scan_backward.hip): c [batch, T + 1] reals; F [batch, nsteps, d + m, d + m], init [batch, d + m, m],
+// states [batch, nsteps, d + m, m], Lam [batch, T, d, m], Pt [batch, T, m, d], X [batch, T, d, d] GOOMs; nsteps = T + (S0 ? 1 : 0)
+int launch_scan_backward_prepare(goom_ctx *ctx, const void *M, const void *S0, const void *P, const void *G, void *c, void *F, void *init, long long T, int d,
+                                 int m, long long batch, int dtype);
+int launch_scan_backward_operands(goom_ctx *ctx, const void *states, const void *P, const void *S0, const void *c, void *Lam, void *Pt, long long T, int d, int m,
+                                  long long batch, int dtype);
+int launch_scan_backward_gradients(goom_ctx *ctx, const void *M, const void *S0, const void *X, const void *states, const void *c, void *gM, void *gS0, long long T,
+                                   int d, int m, long long batch, int dtype);
 int launch_widen_goom(goom_ctx *ctx, const void *z64, void *z128, size_t n); // complex64 GOOMs -> complex128 GOOMs
 int launch_count_nonfinite(goom_ctx *ctx, const void *z, size_t n, int dtype, unsigned long long *count);
 int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t nvec, int d, int dtype);

@@ -82,6 +82,11 @@ def test_argument_validation_without_device(lib):
     assert lib.goom_lmme_backward(None, p, p, p, p, p, p, 2, 8, 2000, 8, 0, 0, None, 0) == EUNSUP
     assert lib.goom_lmme_backward(None, p, p, p, p, p, p, 2, 8, 8, 8, 0, 4, None, 0) == EINVAL and "flags" in err(lib)
     assert lib.goom_lmme_backward(None, p, p, p, p, p, p, 2, 8, 8, 8, 0, 0, None, 0) == EWS
+    assert lib.goom_scan_backward(None, p, None, p, p, p, None, 64, 8, 4, 1, 0, None, None, 0) == EINVAL and "d x d" in err(lib)
+    assert lib.goom_scan_backward(None, p, None, p, p, p, p, 64, 8, 8, 1, 0, None, None, 0) == EINVAL and "initial" in err(lib)
+    assert lib.goom_scan_backward(None, p, p, p, p, p, p, 64, 600, 600, 1, 0, None, None, 0) == EUNSUP
+    assert lib.goom_scan_backward(None, p, p, p, p, p, p, 64, 8, 4, 1, 0, None, None, 0) == EWS
+    assert lib.goom_scan_backward_workspace_bytes(64, 8, 4, 1, 0, None, 1) >= 65 * 12 * (12 + 4) * 8
     assert lib.goom_lmme_backward_workspace_bytes(2, 8, 16, 24, 0, 0) >= 2 * 8 * (8 * 24 + 2 * 8 * 16 + 2 * 16 * 24)
     # the scan on the library's static scratch array: same argument checks, sizes beyond the array refused
     assert lib.goom_scan_static(None, p, None, p, 0, 8, 8, 1, 0, C.byref(o)) == EINVAL and "positive" in err(lib)

@@ -932,6 +932,66 @@ def test_lmme_backward(G, oracle, shape, ctype, flags, spread):
     assert np.all(np.abs(gb.sum(axis=1) - live.sum(axis=1)) <= 4 * rel * mb.sum(axis=1) + 1e-30)
 
 
+@pytest.mark.parametrize("T,d,m,batch,chunk,ctype,with_init", [
+    (40, 8, 8, 2, 0, np.complex64, False), (300, 16, 16, 2, 16, np.complex64, True), (257, 32, 8, 1, 0, np.complex64, True),
+    (60, 64, 64, 1, 0, np.complex64, False), (60, 24, 40, 2, 7, np.complex128, True), (1, 16, 16, 2, 0, np.complex64, True),
+    (30, 100, 60, 1, 0, np.complex64, True), (2000, 16, 16, 1, 0, np.complex64, False), (1, 8, 8, 1, 0, np.complex128, False),
+    (500, 12, 5, 3, 50, np.complex64, True)])
+def test_scan_backward(G, oracle, T, d, m, batch, chunk, ctype, with_init):
+    """Gradients of L = sum grad_p * Re p with respect to the log-magnitudes of every factor and of the initial state,
+    against the oracle's adjoint recurrence fed the same forward states."""
+    comp = np.float32 if ctype == np.complex64 else np.float64
+    Z = oracle.to_goom(si.normal_f32(si.BASE_SEED + 101, 1, batch * T * d * d).reshape(batch, T, d, d).astype(comp))
+    S0 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 102, 2, batch * d * m).reshape(batch, d, m).astype(comp)) if with_init else None
+    Gp = si.normal_f32(si.BASE_SEED + 103, 10, batch * T * d * m).reshape(batch, T, d, m).astype(comp)
+    if T > 3:
+        Z[0, 2, 1, 0] = -np.inf   # a zero entry of a factor
+        Gp[0, 1, 0, 0] = 0.0      # an entry the loss does not see
+    say(f"scan backward T={T} d={d} m={m} batch={batch} chunk={chunk} {np.dtype(ctype).name} init={with_init}")
+    Pd = G.scan(dev(Z), None if S0 is None else dev(S0), chunk_len=chunk)
+    P = host(Pd)
+    gm, gi = G.scan_backward(dev(Z), Pd, dev(Gp), None if S0 is None else dev(S0), chunk_len=chunk)
+    gm = host(gm).astype(np.float64)
+    gi = None if gi is None else host(gi).astype(np.float64)
+    assert np.isfinite(gm).all()
+    if T >= 2000:
+        assert P.real.max() > 2000  # states far outside float range, gradients not
+    rng = np.random.default_rng(6)
+    eta = 2.0 ** -24 if comp == np.float32 else 2.0 ** -53
+    rel = 1e-3 if comp == np.float32 else 1e-9
+    tiny = 2 * float(np.finfo(comp).tiny)
+    worst, worst_well, kept = 0.0, 0.0, []
+    for b in range(batch):
+        s0 = None if S0 is None else S0[b]
+        wm, wi, _ = oracle.scan_backward(Z[b], Gp[b], init=s0, p=P[b])
+        # conditioning, decided by the oracle alone: the adjoints are signed sums.  The probe moves every input's log-magnitude by
+        # a half unit in the last place, independently, and records how far each gradient moves.  The kernels round every one
+        # of the T sums of d + m products an adjoint passes through, a random walk of sqrt(T (d + m)) such half units: every
+        # entry has to lie within the tolerance plus that many times what the probes moved it.
+        tol = rel * np.abs(wm) + 1e-3 * rel * np.abs(wm).max(axis=(-1, -2), keepdims=True) + tiny
+        sens = np.zeros_like(wm)
+        pert = lambda z: None if z is None else (z.astype(np.complex128) + eta * rng.standard_normal(z.shape) * np.where(np.isfinite(z.real), 1.0, 0.0))
+        for _ in range(2):
+            pm, _, _ = oracle.scan_backward(pert(Z[b]), Gp[b], init=pert(s0), p=pert(P[b]))
+            sens = np.maximum(sens, np.abs(pm - wm))
+        noise = math.sqrt(T * (d + m)) * sens
+        worst = max(worst, (np.abs(gm[b] - wm) / (tol + noise)).max())
+        well = noise <= tol
+        kept.append(well.mean())
+        worst_well = max(worst_well, (np.abs(gm[b] - wm) / tol)[well].max())
+        sig = np.abs(wm) > 2 * (tol + noise)
+        assert np.array_equal(np.signbit(gm[b])[sig], np.signbit(wm)[sig])
+        if with_init:
+            assert np.all(np.abs(gi[b] - wi) <= 2 * rel * np.abs(wi) + 1e-2 * rel * np.abs(wi).max() + tiny)
+        if T > 3 and b == 0:
+            assert gm[0, 2, 1, 0] == 0.0
+    say(f"  worst error / bound of grad M {worst:.3g}; entries whose bound is the tolerance alone (within a factor 2): {min(kept):.3f}, "
+        f"their worst error / tolerance {worst_well:.3g}")
+    assert worst <= 1 and min(kept) > (0.1 if comp == np.float32 else 0.99)  # (the share only shows that the bound is not all noise)
+    # the sum rule on the device results alone: the gradients of the last factor's row i add up to those of row i of the last state
+    assert np.all(np.abs(gm[:, -1].sum(axis=2) - Gp[:, -1].astype(np.float64).sum(axis=2)) <= 50 * rel * np.abs(gm[:, -1]).sum(axis=2) + 1e-30)
+
+
 @pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
 def test_signed_log_add(G, oracle, ctype):
     comp = np.float32 if ctype == np.complex64 else np.float64
