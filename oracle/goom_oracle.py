@@ -261,6 +261,18 @@ def affine_scan_backward(a, b, grad_h, h0=None, h=None):
     return gA, gb, gh0, (lre, lsg)
 
 
+def affine_scan_backward_time_invariant(a, b, grad_h, h0=None, h=None):
+    """Backward pass of h_t = A h_{t-1} + b_t with one matrix for all steps (the state-space layer of Section 4.3): the
+    matrix enters every step, so its gradient is the sum over the steps of the time-varying recurrence's gradients.
+    a: [..., d, d]; b, grad_h: [..., T, d].  Returns (dL / d Re A' [..., d, d], dL / d Re b', dL / d Re h0' or None)."""
+    are, _ = _as_working(a)
+    T = np.asarray(b).shape[-2]
+    lead = are.shape[:-2]
+    rep = np.ascontiguousarray(np.broadcast_to(np.asarray(a)[..., None, :, :], lead + (T,) + are.shape[-2:]))
+    gA, gb, gh0, _ = affine_scan_backward(rep, b, grad_h, h0=h0, h=h)
+    return np.asarray(gA.astype(np.longdouble).sum(axis=-3), dtype=np.float64), gb, gh0
+
+
 def scan_backward(mats, grad_p, init=None, p=None):
     """Backward pass of the prefix scan P_t = M_t P_{t-1} over GOOMs (Sections 3.1, 4.1): given grad_p[t, i, k] =
     dL / d Re P'_t[i, k], returns (dL / d Re M' [T, d, d], dL / d Re init' [d, m] or None, adjoints as (re, sg)).

@@ -265,3 +265,42 @@ def test_scan_backward_sum_rules_and_special_cases(oracle):
     D = np.zeros((3, 2, 2)); D[:, 0, 0] = [2.0, 3.0, 4.0]; D[:, 1, 1] = [-1.0, 5.0, 0.5]
     gD, _, _ = oracle.scan_backward(goom_of(D), np.ones((3, 2, 2)))
     assert np.allclose(gD[:, 0, 0], [3, 2, 1]) and np.allclose(gD[:, 1, 1], [3, 2, 1]) and np.all(gD[:, 0, 1] == 0) and np.all(gD[:, 1, 0] == 0)
+
+
+def test_time_invariant_recurrence_backward(oracle):
+    # one matrix for all steps: finite differences move the matrix entry at every step at once
+    rng = np.random.default_rng(61)
+    T, d = 11, 3
+    A = rng.standard_normal((d, d)) * 0.9
+    b = rng.standard_normal((T, d))
+    h0 = rng.standard_normal(d)
+    G = rng.standard_normal((T, d))
+    gA, gb, gh0 = oracle.affine_scan_backward_time_invariant(goom_of(A), goom_of(b), G, h0=goom_of(h0))
+    rep = lambda M: np.broadcast_to(M, (T, d, d))
+    delta = 1e-5
+    for i in range(d):
+        for j in range(d):
+            Ap, Am = A.copy(), A.copy()
+            Ap[i, j] *= math.exp(delta)
+            Am[i, j] *= math.exp(-delta)
+            fd = float((loss_value_domain(rep(Ap), b, h0, G) - loss_value_domain(rep(Am), b, h0, G)) / (2 * delta))
+            assert abs(gA[i, j] - fd) < 1e-6 * max(1.0, abs(fd)), (i, j, gA[i, j], fd)  # (a state near zero: the difference quotient's own error is 1e-7)
+    for (t, i) in [(0, 1), (5, 0), (10, 2)]:
+        bp, bm = b.copy(), b.copy()
+        bp[t, i] *= math.exp(delta)
+        bm[t, i] *= math.exp(-delta)
+        fd = float((loss_value_domain(rep(A), bp, h0, G) - loss_value_domain(rep(A), bm, h0, G)) / (2 * delta))
+        assert abs(gb[t, i] - fd) < 1e-7 * max(1.0, abs(fd))
+    # scalar, no bias, h0 = 1: h_t = a^(t + 1), L = sum_t G_t (t + 1) log a
+    Gs = np.array([[1.0], [10.0], [100.0]])
+    g1, _, g01 = oracle.affine_scan_backward_time_invariant(goom_of(np.array([[1.3]])), goom_of(np.zeros((3, 1))), Gs, h0=goom_of(np.array([1.0])))
+    assert np.allclose(g1, [[321.0]]) and np.allclose(g01, [111.0])
+    # batched leading axes, and the same bias and state gradients as the time-varying pass on the repeated matrix
+    Ab = goom_of(rng.standard_normal((2, d, d)))
+    bb = goom_of(rng.standard_normal((2, T, d)))
+    Gb = rng.standard_normal((2, T, d))
+    gAb, gbb, none = oracle.affine_scan_backward_time_invariant(Ab, bb, Gb)
+    gA1, gb1, _ = oracle.affine_scan_backward_time_invariant(Ab[1], bb[1], Gb[1])
+    assert none is None and np.array_equal(gAb[1], gA1) and np.array_equal(gbb[1], gb1)
+    full, gbf, _, _ = oracle.affine_scan_backward(np.broadcast_to(Ab[:, None], (2, T, d, d)).copy(), bb, Gb)
+    assert np.allclose(gAb, full.sum(axis=1), rtol=1e-13) and np.array_equal(gbb, gbf)
