@@ -584,6 +584,15 @@ def recurrence(g, torch, dev, si):
     res["recurrence_time_invariant"] = {
         "ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1),
         "kernels_ms": kernel_times(g, lambda: g.affine_scan(a1, bz, out=h, time_invariant=True))}
+    # its backward pass: the adjoint recurrence over the one matrix, the matrix's gradient summed over the steps
+    gh = torch.randn((nseq, T, d), device=dev, generator=si.device_generator(251003426 * 10 + 54, dev))
+    sec = timed(torch, lambda: g.affine_scan_backward(a1, bz, h, gh, time_invariant=True))
+    res["recurrence_time_invariant_backward"] = {
+        "ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1),
+        "kernels_ms": kernel_times(g, lambda: g.affine_scan_backward(a1, bz, h, gh, time_invariant=True))}
+    del gh
+    g._ws = None
+    torch.cuda.empty_cache()
     # the elementwise ends of the recurrence as ops of their own, on the states just computed (nseq x T vectors of d):
     # signed log-add (24 B per element) and scaled exponentiation (12 B per element)
     o = torch.empty_like(h)

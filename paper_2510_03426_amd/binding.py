@@ -482,8 +482,9 @@ class Goom:
         self._check(self.lib.goom_from_goom_backward(self._ctx, _ptr(y), _ptr(grad_x), _ptr(out), y.numel(), _dtype_code(y), eps))
         return out
 
-    def affine_scan_backward(self, a, bias, h, grad_h, h0=None, chunk_len: int = 0):
-        """Gradients of a loss with respect to the log-magnitudes of a, bias (and h0), given grad_h = dL / d Re h."""
+    def affine_scan_backward(self, a, bias, h, grad_h, h0=None, chunk_len: int = 0, time_invariant: bool = False):
+        """Gradients of a loss with respect to the log-magnitudes of a, bias (and h0), given grad_h = dL / d Re h.
+        time_invariant: a is [..., d, d], one matrix for all steps, and so is its gradient."""
         torch = self.torch
         code = _dtype_code(a)
         T, d = bias.shape[-2:]
@@ -492,9 +493,10 @@ class Goom:
         for s in lead:
             batch *= s
         comp = torch.float32 if a.dtype == torch.complex64 else torch.float64
-        assert a.shape == lead + (T, d, d) and h.shape == bias.shape and grad_h.shape == bias.shape and grad_h.dtype == comp
-        opts = ScanOpts(chunk_len, 0)
-        ga = torch.empty(lead + (T, d, d), dtype=comp, device=a.device)
+        ashape = lead + ((d, d) if time_invariant else (T, d, d))
+        assert a.shape == ashape and h.shape == bias.shape and grad_h.shape == bias.shape and grad_h.dtype == comp
+        opts = ScanOpts(chunk_len, AFFINE_TIME_INVARIANT if time_invariant else 0)
+        ga = torch.empty(ashape, dtype=comp, device=a.device)
         gb = torch.empty(lead + (T, d), dtype=comp, device=a.device)
         gh0 = torch.empty(lead + (d,), dtype=comp, device=a.device) if h0 is not None else None
         ws, wsn = self.workspace(self.lib.goom_affine_scan_backward_workspace_bytes(T, d, batch, code, C.byref(opts)))

@@ -37,7 +37,10 @@ constexpr int kWalkWaves = 4; // chunks per workgroup
 // ADJ: the adjoint recurrence's factors, read from the forward pass's matrices: step s takes the transpose of matrix
 // steps - s (eight 8-byte loads a pass instead of four 16-byte ones; a load instruction of the wave still covers
 // whole 128-byte lines) and adds left_shift[s] to its log-magnitudes.
-template <int DP, bool TI, bool ADJ = false> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk_kernel(ChainArgs a, long long nchains)
+// IOS (with TI): io_shift[s], a whole number c_s per step: the bias enters as bias[s] e^(-c_s) and the state leaves as h_s e^(c_s),
+// both formed in double beside the vector's exponent (an adjoint recurrence, whose states are e^-1000 and below, fed and
+// read through float GOOMs of ordinary size).
+template <int DP, bool TI, bool ADJ = false, bool IOS = false> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk_kernel(ChainArgs a, long long nchains)
 {
     typedef Comp<float> C;
     constexpr int EPL = DP >= 32 ? 8 : 4; // entries of a row per lane
@@ -67,6 +70,7 @@ template <int DP, bool TI, bool ADJ = false> __global__ __launch_bounds__(kWalkW
     // wave-uniform bases plus 32-bit lane offsets
     const unsigned char *left0 = a.left + item * a.left_batch_stride + t0 * a.left_step_stride;
     const unsigned char *bias0 = a.bias + (size_t)(item * a.steps + t0) * DP * 8;
+    [[maybe_unused]] const float *ios0 = IOS ? a.io_shift + (item * a.steps + t0) : nullptr;
     unsigned char *out0 = a.out_goom ? a.out_goom + (size_t)(item * a.steps + t0) * DP * 8 : nullptr;
     float *scaled0 = a.out_scaled ? a.out_scaled + (size_t)(item * a.steps + t0) * DP : nullptr;
     float *logscale0 = a.out_logscale ? a.out_logscale + (size_t)(item * a.steps + t0) : nullptr;
@@ -210,6 +214,7 @@ template <int DP, bool TI, bool ADJ = false> __global__ __launch_bounds__(kWalkW
         load_bias(tn, bnxt);
         if (t > 0) store_outputs(t - 1);
         if (!TI) scale_rows(cur, shift_cur);
+        [[maybe_unused]] const double cs = IOS ? (double)ios0[t] * 1.44269504088896340736 : 0.0; // c_s in powers of two
         if (vec_zero) {
             // a zero vector has no scale of its own: it takes the bias's, whatever its magnitude (an adjoint
             // recurrence starts at e^-1000 and below), instead of flushing the bias on the scale 2^0
@@ -217,7 +222,10 @@ template <int DP, bool TI, bool ADJ = false> __global__ __launch_bounds__(kWalkW
 #pragma unroll
             for (int q = 0; q < Q; ++q) m = C::max_(m, __builtin_fmaf(bcur[q].x, kHi, -nrow[q]));
             m = C::template group_allmax<64>(m, m);
-            eh = (m > -1.0e30f && m < 1.0e30f) ? (double)__builtin_ceilf(m) : 0.0;
+            if (IOS)
+                eh = (m > -1.0e30f && m < 1.0e30f) ? __builtin_ceil((double)m - cs) : 0.0; // (the vector's exponent stays a whole number)
+            else
+                eh = (m > -1.0e30f && m < 1.0e30f) ? (double)__builtin_ceilf(m) : 0.0;
         }
         const float eh_f = (float)eh;
         float val[Q], barg[Q];
@@ -230,8 +238,13 @@ template <int DP, bool TI, bool ADJ = false> __global__ __launch_bounds__(kWalkW
             part = add_dpp<0xB1>(part);
             part = add_dpp<0x4E>(part);
             // the row's entry of A_t h is part 2^(n + eh); the bias joins it on that scale
-            float x = __builtin_fmaf(bcur[q].x, kHi, -(nrow[q] + eh_f));
-            x = __builtin_fmaf(bcur[q].x, kLo, x);
+            float x;
+            if (IOS) { // the shift and the vector's exponent are large and nearly cancel: in double
+                x = (float)__builtin_fma((double)bcur[q].x, 1.44269504088896340736, -(cs + (double)nrow[q] + eh));
+            } else {
+                x = __builtin_fmaf(bcur[q].x, kHi, -(nrow[q] + eh_f));
+                x = __builtin_fmaf(bcur[q].x, kLo, x);
+            }
             val[q] = part;
             barg[q] = x;
             big = big || x > 64.0f;
@@ -289,7 +302,7 @@ template <int DP, bool TI, bool ADJ = false> __global__ __launch_bounds__(kWalkW
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         // the state is mantissas 2^eh
-        if (out0) pend_goom = float2{C::out_re_f(mine, (float)eh), mine < 0.0f ? C::pi() : 0.0f};
+        if (out0) pend_goom = float2{C::out_re_f(mine, IOS ? (float)(eh + cs) : (float)eh), mine < 0.0f ? C::pi() : 0.0f};
         if (scaled0) {
             // the scaled exponentiation (Section 4.3, eq. 27) on the factored vector: with c = log of the largest magnitude, exp(z_i - c + 2) is the
             // mantissa over the largest mantissa, times e^2; the vector's exponent only enters c
@@ -694,13 +707,13 @@ template <typename R> __global__ __launch_bounds__(256) void replicate_power_ker
     }
 }
 
-template <int DP, bool TI, bool ADJ = false> int launch_walk(goom_ctx *ctx, const ChainArgs &args, long long nchains, const char *label)
+template <int DP, bool TI, bool ADJ = false, bool IOS = false> int launch_walk(goom_ctx *ctx, const ChainArgs &args, long long nchains, const char *label)
 {
     const long long grid = (nchains + kWalkWaves - 1) / kWalkWaves;
     if (grid <= 0) return GOOM_OK;
     if (grid > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many chains for one launch (%lld)", nchains);
     goom::prof_begin(ctx, label);
-    hipLaunchKernelGGL((affine_walk_kernel<DP, TI, ADJ>), dim3((unsigned)grid), dim3(kWalkWaves * 64), 0, ctx->stream, args, nchains);
+    hipLaunchKernelGGL((affine_walk_kernel<DP, TI, ADJ, IOS>), dim3((unsigned)grid), dim3(kWalkWaves * 64), 0, ctx->stream, args, nchains);
     goom::prof_end(ctx);
     return goom::check_hip(ctx, hipGetLastError(), "launch affine_walk_kernel");
 }
@@ -739,9 +752,12 @@ bool affine_walk_applies(const ChainArgs &args, int dp)
 int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long nchains, const char *label)
 {
     const bool ti = args.left_step_stride == 0;
-    if (args.left_shift) { // the adjoint recurrence: transposed factors in reverse order
-        if (ti) return goom::fail(ctx, GOOM_EUNSUPPORTED, "transposed factors in reverse order: one matrix per step");
+    if (args.left_shift) { // the adjoint recurrence: transposed factors in reverse order (a step stride of 0: one matrix, shifted anew every step)
         return dp == 16 ? launch_walk<16, false, true>(ctx, args, nchains, label) : launch_walk<32, false, true>(ctx, args, nchains, label);
+    }
+    if (args.io_shift) { // bias and states rescaled step by step: over one matrix, GOOM or factored outputs
+        if (!ti || args.out_scaled) return goom::fail(ctx, GOOM_EUNSUPPORTED, "rescaled bias and states: the matrix-vector walk over one matrix only");
+        return dp == 16 ? launch_walk<16, true, false, true>(ctx, args, nchains, label) : launch_walk<32, true, false, true>(ctx, args, nchains, label);
     }
     if (dp == 16) return ti ? launch_walk<16, true>(ctx, args, nchains, label) : launch_walk<16, false>(ctx, args, nchains, label);
     return ti ? launch_walk<32, true>(ctx, args, nchains, label) : launch_walk<32, false>(ctx, args, nchains, label);
@@ -753,8 +769,7 @@ int dispatch_affine_chunk_f64(goom_ctx *ctx, const ChainArgs &args, int dp, long
     if (!((dp == 16 || dp == 32) && args.n == dp && args.d == dp && args.m == dp + 1 && args.init_mode == 0 && args.out_goom == nullptr &&
           args.out_fact_steps == nullptr && args.out_fact_final != nullptr && args.fact_cols == dp + 16))
         return goom::fail(ctx, GOOM_EUNSUPPORTED, "double-state chunk products are built for d = 16 and 32");
-    if (args.left_shift) { // the adjoint recurrence: transposed factors in reverse order
-        if (args.left_step_stride == 0) return goom::fail(ctx, GOOM_EUNSUPPORTED, "transposed factors in reverse order: one matrix per step");
+    if (args.left_shift) { // the adjoint recurrence: transposed factors in reverse order (a step stride of 0: one matrix, shifted anew every step)
         return dp == 16 ? launch_chunk_f64<16, 1, false, true>(ctx, args, grid, label) : launch_chunk_f64<32, 2, false, true>(ctx, args, grid, label);
     }
     if (args.left_step_stride == 0) // one matrix at every step

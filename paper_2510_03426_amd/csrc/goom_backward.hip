@@ -93,7 +93,7 @@ template <typename R, int NW> __global__ __launch_bounds__(NW * 64) void bwd_pre
                                                                                             const typename C2<R>::type *__restrict__ H,
                                                                                             const R *__restrict__ G, typename C2<R>::type *__restrict__ At,
                                                                                             typename C2<R>::type *__restrict__ gt, long long T, int d,
-                                                                                            long long nsteps, int direct)
+                                                                                            long long nsteps, int direct, int one_matrix)
 {
     typedef typename C2<R>::type c2;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -112,7 +112,7 @@ template <typename R, int NW> __global__ __launch_bounds__(NW * 64) void bwd_pre
         for (int e = lane; e < nn; e += 64) dst[e] = c2{ninf, (R)0};
     } else {
         const R delta = ct - state_scale<R>(H + (size_t)(b * T + t + 1) * d, d); // c_t - c_{t+1}, a whole number
-        const c2 *src = A + (size_t)(b * T + (T - s)) * d * d;
+        const c2 *src = A + (one_matrix ? (size_t)b : (size_t)(b * T + (T - s))) * d * d; // (one_matrix: the same factor at every step)
         if (direct) { // a matrix too large for LDS (complex128 above 96 x 96): strided reads
             for (int e = lane; e < nn; e += 64) {
                 c2 v = src[(e % d) * d + e / d];
@@ -165,8 +165,9 @@ template <typename R, int NW> __global__ __launch_bounds__(NW * 64) void bwd_pre
 // matrix), and gt.  A group of lanes per (b, s), so that a wave serves two to eight steps of short vectors.
 template <typename R> __global__ __launch_bounds__(256) void bwd_shift_kernel(const typename C2<R>::type *__restrict__ H, const R *__restrict__ G,
                                                                              float *__restrict__ shift, typename C2<R>::type *__restrict__ gt,
-                                                                             long long T, int d, long long nsteps, int group)
+                                                                             long long T, int d, long long nsteps, int group, int absolute)
 {
+    // absolute: shift[b, s] = c_t itself (for a scan that rescales its bias and its stored states by it, its factors unchanged)
     // a group of `group` lanes (8, 16, 32 or 64: the power of two that holds d, or the whole wave) per (b, s)
     typedef typename C2<R>::type c2;
     const int lane = threadIdx.x & 63, sub = lane % group;
@@ -193,7 +194,7 @@ template <typename R> __global__ __launch_bounds__(256) void bwd_shift_kernel(co
     const R ct = scale_of(t);
     const R cnext = scale_of(t + 1);
     if (!active) return;
-    if (sub == 0) shift[b * T + s] = s == 0 ? (float)ninf : (float)(ct - cnext);
+    if (sub == 0) shift[b * T + s] = absolute ? (float)ct : s == 0 ? (float)ninf : (float)(ct - cnext);
     for (int i = sub; i < d; i += group) {
         const R gv = G[(size_t)(b * T + t) * d + i];
         const c2 h = H[(size_t)(b * T + t) * d + i];
@@ -217,7 +218,8 @@ template <typename R> __global__ __launch_bounds__(kGradWaves * 64) void bwd_gra
                                                                                          const typename C2<R>::type *__restrict__ h0,
                                                                                          const typename C2<R>::type *__restrict__ H,
                                                                                          const typename C2<R>::type *__restrict__ mu, R *__restrict__ gA,
-                                                                                         R *__restrict__ gb, long long T, int d, long long nsteps)
+                                                                                         R *__restrict__ gb, long long T, int d, long long nsteps,
+                                                                                         double *__restrict__ U, double *__restrict__ V)
 {
     typedef typename C2<R>::type c2;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -258,8 +260,26 @@ template <typename R> __global__ __launch_bounds__(kGradWaves * 64) void bwd_gra
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const c2 *ap = A + (size_t)(b * T + t) * d * d;
-    R *op = gA + (size_t)(b * T + t) * d * d;
+    if (U) {
+        // one matrix for all steps: its gradient is A[i, j] sum_t lam_t[i] h_{t-1}[j].  This step's factors as doubles,
+        // u[i] = lam_t[i] e^r and v[j] = h_{t-1}[j] e^(-r), r the largest log-magnitude of h_{t-1} (|v| <= 1; u is of the
+        // size of the gradient's terms)
+        double r = ninf;
+        for (int j = lane; j < d; j += 64) r = pre[j] > r ? pre[j] : r;
+        for (int sft = 32; sft > 0; sft >>= 1) {
+            const double o = __shfl_xor(r, sft, 64);
+            r = o > r ? o : r;
+        }
+        const bool any = r > ninf && r < -ninf;
+        for (int i = lane; i < d; i += 64) {
+            const double u = (any && lre[i] > ninf) ? exp(lre[i] + r) : 0.0;
+            const double v = (any && pre[i] > ninf) ? exp(pre[i] - r) : 0.0;
+            U[(size_t)(b * T + t) * d + i] = lneg[i] ? -u : u;
+            V[(size_t)(b * T + t) * d + i] = pneg[i] ? -v : v;
+        }
+    }
+    const c2 *ap = U ? nullptr : A + (size_t)(b * T + t) * d * d;
+    R *op = U ? nullptr : gA + (size_t)(b * T + t) * d * d;
     auto one = [&](int e, c2 a) {
         const int i = e / d, j = e - i * d;
         const double s = lre[i] + (double)a.x + pre[j];
@@ -268,7 +288,7 @@ template <typename R> __global__ __launch_bounds__(kGradWaves * 64) void bwd_gra
         const bool neg = (lneg[i] ^ pneg[j] ^ (odd_phase<R>(a.y) ? 1 : 0)) != 0;
         return (R)(neg ? -v : v);
     };
-    const int nn = d * d;
+    const int nn = U ? 0 : d * d;
     if (sizeof(R) == 4 && (nn & 1) == 0) {
         // two adjacent entries per lane and pass: one 16-byte load, one 8-byte store
         const float4 *ap4 = reinterpret_cast<const float4 *>(ap);
@@ -303,6 +323,73 @@ template <typename R> __global__ __launch_bounds__(128) void bwd_h0_kernel(const
         for (int i = 0; i < d; ++i) acc += (double)gA[((size_t)b * T * d + i) * d + j];
         gh0[(size_t)b * d + j] = (R)acc;
     }
+}
+
+// One matrix for all steps: partial[b, q] = sum over the steps of split q of u_t v_t^T, DP x DP doubles (rows and columns
+// beyond d are zero).  Eight steps at a time through LDS; a thread owns DP * DP / 256 neighbouring entries of one row.
+constexpr int kOuterSteps = 8;
+
+template <int DP> __global__ __launch_bounds__(256) void bwd_outer_kernel(const double *__restrict__ U, const double *__restrict__ V,
+                                                                          double *__restrict__ partial, long long T, int d, int nsplit)
+{
+    constexpr int EPT = DP * DP / 256;
+    __shared__ double u[kOuterSteps][DP], v[kOuterSteps][DP];
+    const long long b = blockIdx.x / nsplit;
+    const int q = (int)(blockIdx.x - b * nsplit);
+    const long long per = (T + nsplit - 1) / nsplit, t0 = q * per, t1 = t0 + per < T ? t0 + per : T;
+    const int e0 = threadIdx.x * EPT, i = e0 / DP, j0 = e0 - i * DP;
+    double acc[EPT];
+#pragma unroll
+    for (int k = 0; k < EPT; ++k) acc[k] = 0.0;
+    for (long long tb = t0; tb < t1; tb += kOuterSteps) {
+        for (int x = threadIdx.x; x < kOuterSteps * DP; x += 256) {
+            const int kb = x / DP, c = x - kb * DP;
+            const bool in = tb + kb < t1 && c < d;
+            u[kb][c] = in ? U[(size_t)(b * T + tb + kb) * d + c] : 0.0;
+            v[kb][c] = in ? V[(size_t)(b * T + tb + kb) * d + c] : 0.0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kb = 0; kb < kOuterSteps; ++kb) {
+            const double ui = u[kb][i];
+#pragma unroll
+            for (int k = 0; k < EPT; ++k) acc[k] += ui * v[kb][j0 + k];
+        }
+        __syncthreads();
+    }
+    double *out = partial + (size_t)blockIdx.x * DP * DP + e0;
+#pragma unroll
+    for (int k = 0; k < EPT; ++k) out[k] = acc[k];
+}
+
+// gA[b, i, j] = A[b, i, j] sum_q partial[b, q, i, j] (in the order of q);  gh0[b, j] = v_0[j] sum_i u_0[i] A[b, i, j]
+template <typename R> __global__ __launch_bounds__(256) void bwd_outer_finish_kernel(const typename C2<R>::type *__restrict__ A, const double *__restrict__ partial,
+                                                                                     const double *__restrict__ U, const double *__restrict__ V,
+                                                                                     R *__restrict__ gA, R *__restrict__ gh0, long long T, int d, int dp, int nsplit)
+{
+    typedef typename C2<R>::type c2;
+    const long long b = blockIdx.x;
+    const double ninf = -__builtin_huge_val();
+    for (int e = threadIdx.x; e < d * d; e += 256) {
+        const int i = e / d, j = e - i * d;
+        double acc = 0.0;
+        for (int q = 0; q < nsplit; ++q) acc += partial[((size_t)b * nsplit + q) * dp * dp + (size_t)i * dp + j];
+        const c2 a = A[(size_t)b * d * d + e];
+        // (through the logarithm of the sum: the entry alone may lie outside the range of a double)
+        const double mag = (acc != 0.0 && (double)a.x > ninf) ? exp((double)a.x + log(__builtin_fabs(acc))) : 0.0;
+        gA[(size_t)b * d * d + e] = (R)((acc < 0.0) != odd_phase<R>(a.y) ? -mag : mag);
+    }
+    if (gh0)
+        for (int j = threadIdx.x; j < d; j += 256) {
+            double acc = 0.0;
+            for (int i = 0; i < d; ++i) {
+                const c2 a = A[(size_t)b * d * d + (size_t)i * d + j];
+                const double ui = U[(size_t)b * T * d + i];
+                const double mag = (ui != 0.0 && (double)a.x > ninf) ? exp((double)a.x + log(__builtin_fabs(ui))) : 0.0;
+                acc += (ui < 0.0) != odd_phase<R>(a.y) ? -mag : mag;
+            }
+            gh0[(size_t)b * d + j] = (R)(acc * V[(size_t)b * T * d + j]);
+        }
 }
 
 unsigned blocks_for(size_t n)
@@ -344,7 +431,7 @@ int launch_from_goom_backward(goom_ctx *ctx, const void *y, const void *gx, void
 }
 
 template <typename R, int NW> static int bwd_prepare_launch(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d,
-                                                           long long batch)
+                                                           long long batch, bool one_matrix)
 {
     typedef typename C2<R>::type c2;
     const size_t tile_bytes = (size_t)d * (d + 1) * sizeof(c2);
@@ -357,21 +444,30 @@ template <typename R, int NW> static int bwd_prepare_launch(goom_ctx *ctx, const
     const long long nsteps = batch * T;
     prof_begin(ctx, "affine_backward_prepare_operands");
     hipLaunchKernelGGL(kern, dim3((unsigned)((nsteps + NW - 1) / NW)), dim3(NW * 64), lds, ctx->stream, static_cast<const c2 *>(A), static_cast<const c2 *>(H),
-                       static_cast<const R *>(G), static_cast<c2 *>(At), static_cast<c2 *>(gt), T, d, nsteps, direct);
+                       static_cast<const R *>(G), static_cast<c2 *>(At), static_cast<c2 *>(gt), T, d, nsteps, direct, one_matrix ? 1 : 0);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch bwd_prepare_kernel");
 }
 
 // waves (steps) per workgroup: as many as the matrices' LDS tiles allow
-template <typename R> static int bwd_prepare_t(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d, long long batch)
+template <typename R> static int bwd_prepare_t(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d, long long batch,
+                                               bool one_matrix)
 {
     const size_t tile = (size_t)d * (d + 1) * 2 * sizeof(R);
-    if (4 * tile <= 64 * 1024) return bwd_prepare_launch<R, 4>(ctx, A, H, G, At, gt, T, d, batch);
-    if (2 * tile <= 96 * 1024) return bwd_prepare_launch<R, 2>(ctx, A, H, G, At, gt, T, d, batch);
-    return bwd_prepare_launch<R, 1>(ctx, A, H, G, At, gt, T, d, batch);
+    if (4 * tile <= 64 * 1024) return bwd_prepare_launch<R, 4>(ctx, A, H, G, At, gt, T, d, batch, one_matrix);
+    if (2 * tile <= 96 * 1024) return bwd_prepare_launch<R, 2>(ctx, A, H, G, At, gt, T, d, batch, one_matrix);
+    return bwd_prepare_launch<R, 1>(ctx, A, H, G, At, gt, T, d, batch, one_matrix);
 }
 
-template <typename R> static int bwd_shift_t(goom_ctx *ctx, const void *H, const void *G, float *shift, void *gt, long long T, int d, long long batch)
+// At[b] = A[b]^T, d x d (one matrix per batch item)
+template <typename R> __global__ __launch_bounds__(256) void bwd_transpose_kernel(const typename C2<R>::type *__restrict__ A, typename C2<R>::type *__restrict__ At, int d)
+{
+    const size_t base = (size_t)blockIdx.x * d * d;
+    for (int e = threadIdx.x; e < d * d; e += 256) At[base + e] = A[base + (size_t)(e % d) * d + e / d];
+}
+
+template <typename R> static int bwd_shift_t(goom_ctx *ctx, const void *H, const void *G, float *shift, void *gt, long long T, int d, long long batch,
+                                             const void *A = nullptr, void *At = nullptr)
 {
     typedef typename C2<R>::type c2;
     const long long nsteps = batch * T;
@@ -379,18 +475,27 @@ template <typename R> static int bwd_shift_t(goom_ctx *ctx, const void *H, const
     const int group = d <= 8 ? 8 : d <= 16 ? 16 : d <= 32 ? 32 : 64;
     const long long per_block = 256 / group;
     hipLaunchKernelGGL(bwd_shift_kernel<R>, dim3((unsigned)((nsteps + per_block - 1) / per_block)), dim3(256), 0, ctx->stream, static_cast<const c2 *>(H),
-                       static_cast<const R *>(G), shift, static_cast<c2 *>(gt), T, d, nsteps, group);
+                       static_cast<const R *>(G), shift, static_cast<c2 *>(gt), T, d, nsteps, group, At ? 1 : 0);
+    if (At) hipLaunchKernelGGL(bwd_transpose_kernel<R>, dim3((unsigned)batch), dim3(256), 0, ctx->stream, static_cast<const c2 *>(A), static_cast<c2 *>(At), d);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch bwd_shift_kernel");
 }
 
 // At: the transposed, reversed, rescaled copy of A; or NULL, and then shift receives the shifts alone
 int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, float *shift, void *gt, long long T, int d,
-                                   long long batch, int dtype)
+                                   long long batch, int dtype, bool one_matrix)
 {
     if (batch * T > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
     if (!At) return dtype == GOOM_C64 ? bwd_shift_t<float>(ctx, H, G, shift, gt, T, d, batch) : bwd_shift_t<double>(ctx, H, G, shift, gt, T, d, batch);
-    return dtype == GOOM_C64 ? bwd_prepare_t<float>(ctx, A, H, G, At, gt, T, d, batch) : bwd_prepare_t<double>(ctx, A, H, G, At, gt, T, d, batch);
+    return dtype == GOOM_C64 ? bwd_prepare_t<float>(ctx, A, H, G, At, gt, T, d, batch, one_matrix) : bwd_prepare_t<double>(ctx, A, H, G, At, gt, T, d, batch, one_matrix);
+}
+
+// One matrix for all steps, scan over the matrix itself: At [batch, d, d] = A^T, shift[b, s] = c_t, gt as above
+int launch_affine_backward_prepare_one_matrix(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, float *shift, void *gt, long long T, int d,
+                                              long long batch, int dtype)
+{
+    if (batch * T > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
+    return dtype == GOOM_C64 ? bwd_shift_t<float>(ctx, H, G, shift, gt, T, d, batch, A, At) : bwd_shift_t<double>(ctx, H, G, shift, gt, T, d, batch, A, At);
 }
 
 template <typename R> static int bwd_grad_t(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
@@ -402,7 +507,8 @@ template <typename R> static int bwd_grad_t(goom_ctx *ctx, const void *A, const 
     prof_begin(ctx, "affine_backward_gradients");
     hipLaunchKernelGGL(bwd_grad_kernel<R>, dim3((unsigned)((nsteps + kGradWaves - 1) / kGradWaves)), dim3(kGradWaves * 64), lds, ctx->stream,
                        static_cast<const c2 *>(A), static_cast<const c2 *>(bias), static_cast<const c2 *>(h0), static_cast<const c2 *>(H),
-                       static_cast<const c2 *>(mu), static_cast<R *>(gA), static_cast<R *>(gb), T, d, nsteps);
+                       static_cast<const c2 *>(mu), static_cast<R *>(gA), static_cast<R *>(gb), T, d, nsteps, static_cast<double *>(nullptr),
+                       static_cast<double *>(nullptr));
     if (gh0) hipLaunchKernelGGL(bwd_h0_kernel<R>, dim3((unsigned)batch), dim3(128), 0, ctx->stream, static_cast<const R *>(gA), static_cast<R *>(gh0), T, d);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch bwd_grad_kernel");
@@ -414,6 +520,39 @@ int launch_affine_backward_gradients(goom_ctx *ctx, const void *A, const void *b
     if (batch * T > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
     return dtype == GOOM_C64 ? bwd_grad_t<float>(ctx, A, bias, h0, H, mu, gA, gb, gh0, T, d, batch)
                              : bwd_grad_t<double>(ctx, A, bias, h0, H, mu, gA, gb, gh0, T, d, batch);
+}
+
+// One matrix for all steps.  U, V: [batch, T, d] doubles; partial: [batch, nsplit, dp, dp] doubles (dp: d padded to 16, 32, 64 or 128)
+template <typename R> static int bwd_grad_ti_t(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA, void *gb,
+                                               void *gh0, double *U, double *V, double *partial, int nsplit, long long T, int d, long long batch)
+{
+    typedef typename C2<R>::type c2;
+    const size_t lds = (size_t)kGradWaves * d * (2 * sizeof(double) + 2 * sizeof(int));
+    const long long nsteps = batch * T;
+    const int dp = d <= 16 ? 16 : d <= 32 ? 32 : d <= 64 ? 64 : 128;
+    prof_begin(ctx, "affine_backward_gradients");
+    hipLaunchKernelGGL(bwd_grad_kernel<R>, dim3((unsigned)((nsteps + kGradWaves - 1) / kGradWaves)), dim3(kGradWaves * 64), lds, ctx->stream,
+                       static_cast<const c2 *>(nullptr), static_cast<const c2 *>(bias), static_cast<const c2 *>(h0), static_cast<const c2 *>(H),
+                       static_cast<const c2 *>(mu), static_cast<R *>(nullptr), static_cast<R *>(gb), T, d, nsteps, U, V);
+    const dim3 grid((unsigned)(batch * nsplit));
+    if (dp == 16) hipLaunchKernelGGL(bwd_outer_kernel<16>, grid, dim3(256), 0, ctx->stream, U, V, partial, T, d, nsplit);
+    else if (dp == 32) hipLaunchKernelGGL(bwd_outer_kernel<32>, grid, dim3(256), 0, ctx->stream, U, V, partial, T, d, nsplit);
+    else if (dp == 64) hipLaunchKernelGGL(bwd_outer_kernel<64>, grid, dim3(256), 0, ctx->stream, U, V, partial, T, d, nsplit);
+    else hipLaunchKernelGGL(bwd_outer_kernel<128>, grid, dim3(256), 0, ctx->stream, U, V, partial, T, d, nsplit);
+    hipLaunchKernelGGL(bwd_outer_finish_kernel<R>, dim3((unsigned)batch), dim3(256), 0, ctx->stream, static_cast<const c2 *>(A), partial, U, V,
+                       static_cast<R *>(gA), static_cast<R *>(gh0), T, d, dp, nsplit);
+    prof_end(ctx);
+    return check_hip(ctx, hipGetLastError(), "launch bwd_outer_kernel");
+}
+
+int launch_affine_backward_gradients_one_matrix(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
+                                                void *gb, void *gh0, void *U, void *V, void *partial, int nsplit, long long T, int d, long long batch, int dtype)
+{
+    if (batch * T > 0x7fffffffLL || batch * nsplit > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
+    return dtype == GOOM_C64 ? bwd_grad_ti_t<float>(ctx, A, bias, h0, H, mu, gA, gb, gh0, static_cast<double *>(U), static_cast<double *>(V),
+                                                    static_cast<double *>(partial), nsplit, T, d, batch)
+                             : bwd_grad_ti_t<double>(ctx, A, bias, h0, H, mu, gA, gb, gh0, static_cast<double *>(U), static_cast<double *>(V),
+                                                     static_cast<double *>(partial), nsplit, T, d, batch);
 }
 
 } // namespace goom

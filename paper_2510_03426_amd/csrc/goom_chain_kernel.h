@@ -65,6 +65,10 @@ struct ChainArgs {
     // NULL, or [batch, steps] floats; the factor of step s is then the transpose of matrix steps - s of the array
     // `left` (any matrix for s = 0) with left_shift[s] added to every log-magnitude (-inf: a zero matrix)
     const float *left_shift;
+    // the matrix-vector walk over one matrix for all steps only: NULL, or [batch, steps] floats (whole numbers); the bias of step s
+    // is then bias[s] e^(-io_shift[s]) and the state written for step s is h_s e^(+io_shift[s]): values far from 1 pass
+    // through GOOM arrays of float components with log-magnitudes of ordinary size
+    const float *io_shift;
 };
 
 template <typename R> struct Comp;

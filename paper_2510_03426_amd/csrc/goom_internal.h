@@ -98,6 +98,7 @@ struct ChainLaunch {
     int fact_f64;         // float kernels of the recurrence: factored matrices read / written have double mantissas
     int acc_f64;          // chunk products of the recurrence with the running product in double (float GOOM factors)
     const float *left_shift; // NULL, or [batch, steps]: factors read transposed in reverse order, log-magnitudes shifted (see ChainArgs)
+    const float *io_shift;   // NULL, or [batch, steps]: bias and stored states rescaled by e^(-+io_shift[s]) (see ChainArgs)
     const char *label;    // phase name for profiling records
 };
 int launch_chain(goom_ctx *ctx, const ChainLaunch &a);
@@ -163,7 +164,7 @@ int launch_matrix_probe(goom_ctx *ctx, void *sink, long long iters, int dtype);
 int launch_to_goom_backward(goom_ctx *ctx, const void *x, const void *g, void *gx, size_t n, int dtype, double eps);
 int launch_from_goom_backward(goom_ctx *ctx, const void *y, const void *gx, void *g, size_t n, int dtype, double eps);
 int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, float *shift, void *gt, long long T, int d,
-                                   long long batch, int dtype);
+                                   long long batch, int dtype, bool one_matrix = false); // one_matrix: A is [batch, d, d], every step's factor
 int launch_affine_backward_gradients(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
                                      void *gb, void *gh0, long long T, int d, long long batch, int dtype);
 // backward of LMME (goom_lmme_backward.hip): shifts r [batch, n], c [batch, m]; W [batch, n, m], At [batch, d, n], Bt [batch, m, d] GOOMs
@@ -179,6 +180,11 @@ int launch_scan_backward_operands(goom_ctx *ctx, const void *states, const void 
                                   long long batch, int dtype);
 int launch_scan_backward_gradients(goom_ctx *ctx, const void *M, const void *S0, const void *X, const void *states, const void *c, void *gM, void *gS0, long long T,
                                    int d, int m, long long batch, int dtype);
+int launch_affine_backward_prepare_one_matrix(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, float *shift, void *gt, long long T, int d,
+                                              long long batch, int dtype); // At [batch, d, d] = A^T; shift[b, s] = c_{T-1-s}
+// one matrix for all steps: gA [batch, d, d]; U, V [batch, T, d] doubles, partial [batch, nsplit, dp, dp] doubles (dp = d padded to 16, 32, 64, 128)
+int launch_affine_backward_gradients_one_matrix(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
+                                                void *gb, void *gh0, void *U, void *V, void *partial, int nsplit, long long T, int d, long long batch, int dtype);
 int launch_widen_goom(goom_ctx *ctx, const void *z64, void *z128, size_t n); // complex64 GOOMs -> complex128 GOOMs
 int launch_count_nonfinite(goom_ctx *ctx, const void *z, size_t n, int dtype, unsigned long long *count);
 int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t nvec, int d, int dtype);

@@ -992,6 +992,54 @@ def test_scan_backward(G, oracle, T, d, m, batch, chunk, ctype, with_init):
     assert np.all(np.abs(gm[:, -1].sum(axis=2) - Gp[:, -1].astype(np.float64).sum(axis=2)) <= 50 * rel * np.abs(gm[:, -1]).sum(axis=2) + 1e-30)
 
 
+@pytest.mark.parametrize("T,d,batch,chunk,ctype,with_h0,gain", [
+    (3000, 32, 2, 0, np.complex64, True, 1.02), (1000, 16, 3, 0, np.complex64, False, 1.02), (300, 8, 2, 16, np.complex64, True, 1.02),
+    (200, 64, 1, 40, np.complex64, True, 0.95), (150, 16, 2, 16, np.complex128, True, 1.02), (40, 100, 1, 8, np.complex128, False, 1.0),
+    (1, 32, 2, 0, np.complex64, True, 1.02), (700, 32, 1, 7, np.complex64, False, 1.1)])
+def test_affine_scan_backward_time_invariant(G, oracle, T, d, batch, chunk, ctype, with_h0, gain):
+    """The recurrence with one matrix for all steps (the paper's state-space layer): the matrix's gradient is the sum over
+    the steps of lam_t[i] A[i, j] h_{t-1}[j]; bias and initial-state gradients as in the time-varying pass."""
+    comp = np.float32 if ctype == np.complex64 else np.float64
+    A, _ = si.recurrence_inputs(si.BASE_SEED + 111, batch, 1, d, gain=gain)
+    _, b = si.recurrence_inputs(si.BASE_SEED + 112, batch, T, d)
+    Az, bz = oracle.to_goom(A[:, 0].astype(comp)), oracle.to_goom(b.astype(comp))
+    h0 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 113, 9, batch * d).reshape(batch, d).astype(comp)) if with_h0 else None
+    Gh = si.normal_f32(si.BASE_SEED + 114, 10, batch * T * d).reshape(batch, T, d).astype(comp)
+    say(f"time-invariant affine backward T={T} d={d} batch={batch} chunk={chunk} {np.dtype(ctype).name} h0={with_h0}")
+    Hd = G.affine_scan(dev(Az), dev(bz), None if h0 is None else dev(h0), chunk_len=chunk, time_invariant=True)
+    H = host(Hd)
+    ga, gb, gh0 = G.affine_scan_backward(dev(Az), dev(bz), Hd, dev(Gh), None if h0 is None else dev(h0), chunk_len=chunk, time_invariant=True)
+    ga, gb = host(ga).astype(np.float64), host(gb).astype(np.float64)
+    assert ga.shape == (batch, d, d)
+    rep = lambda a_: np.ascontiguousarray(np.broadcast_to(a_[:, None], (batch, T, d, d)))
+    per_step, wb, wh0, _ = oracle.affine_scan_backward(rep(Az), bz, Gh, h0=h0, h=H)
+    wa = per_step.sum(axis=1)
+    mass = np.abs(per_step).sum(axis=1)  # the magnitudes of the T terms of every entry
+    want_ti, _, _ = oracle.affine_scan_backward_time_invariant(Az, bz, Gh, h0=h0, h=H)
+    assert np.allclose(wa, want_ti, rtol=1e-12, atol=1e-300)
+    # conditioning, decided by the oracle alone (as for the time-varying pass): probes of half a unit in the last place
+    rng = np.random.default_rng(7)
+    eta = 2.0 ** -24 if comp == np.float32 else 2.0 ** -53
+    rel = 1e-3 if comp == np.float32 else 1e-9
+    tiny = 2 * float(np.finfo(comp).tiny)
+    tol_a = rel * mass + tiny  # (a sum of T terms of like sign or not: against the sum of their magnitudes)
+    tol_b = rel * np.abs(wb) + 1e-3 * rel * np.abs(wb).max(axis=-1, keepdims=True) + tiny
+    sens_a, sens_b = np.zeros_like(wa), np.zeros_like(wb)
+    pert = lambda z: None if z is None else (z.astype(np.complex128) + eta * rng.standard_normal(z.shape) * np.where(np.isfinite(z.real), 1.0, 0.0))
+    for _ in range(2):
+        pa, pb, _, _ = oracle.affine_scan_backward(rep(pert(Az)), pert(bz), Gh, h0=pert(h0), h=pert(H))
+        sens_a, sens_b = np.maximum(sens_a, np.abs(pa.sum(axis=1) - wa)), np.maximum(sens_b, np.abs(pb - wb))
+    well_a, well_b = sens_a <= tol_a / 16, sens_b <= tol_b / 16
+    ra = (np.abs(ga - wa) / tol_a)[well_a].max() if well_a.any() else 0.0
+    rb = (np.abs(gb - wb) / tol_b)[well_b].max()
+    say(f"  worst error / tolerance: grad A {ra:.3g}, grad bias {rb:.3g}; left out as ill conditioned {1 - well_a.mean():.2e} / {1 - well_b.mean():.2e}; "
+        f"largest |grad A| / mass {np.max(np.abs(wa) / mass):.3g}")
+    assert ra <= 1 and rb <= 1 and well_a.mean() > 0.7 and well_b.mean() > 0.7
+    if with_h0:
+        gh0 = host(gh0).astype(np.float64)
+        assert np.all(np.abs(gh0 - wh0) <= 2e-3 * np.abs(wh0) + 1e-4 * np.abs(wh0).max())
+
+
 @pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
 def test_signed_log_add(G, oracle, ctype):
     comp = np.float32 if ctype == np.complex64 else np.float64
