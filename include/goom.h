@@ -425,7 +425,7 @@ size_t goom_scan_backward_workspace_bytes(int64_t T, int d, int m, int64_t batch
  * grad_A: [batch, T, d, d] reals; grad_bias: NULL or [batch, T, d] reals; grad_h0: NULL or [batch, d] reals (needs
  * h0).  opts->flags: 0, or GOOM_AFFINE_TIME_INVARIANT for the recurrence with one matrix per batch item (the paper's
  * state-space layer, Section 4.3): A and grad_A are [batch, d, d], grad_A[b, i, j] = A[i, j] sum_t lam_t[i] h_{t-1}[j],
- * summed in double in a fixed order (the workspace then also holds two doubles per state entry).  workspace: goom_affine_scan_backward_workspace_bytes(...) bytes: a few vectors per
+ * summed in double in a fixed order.  workspace: goom_affine_scan_backward_workspace_bytes(...) bytes: a few vectors per
  * step for complex64 with d = 16 or 32 and more than one chunk (the scan reads A transposed itself); otherwise it
  * also holds a transposed copy of A and is a little larger than A. */
 int goom_affine_scan_backward(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H,

@@ -1107,7 +1107,7 @@ struct AffineBackwardPlan {
     bool same_factor; // one_matrix, and the adjoint scan runs over A^T itself, its bias and states rescaled step by step
     int nsplit;      // one_matrix: spans of steps whose outer products are summed by one workgroup each
     size_t at_bytes, vec_bytes, scan_bytes, uv_bytes, partial_bytes;
-    size_t total() const { return at_bytes + 2 * vec_bytes + scan_bytes + 2 * uv_bytes + partial_bytes; }
+    size_t total() const { return at_bytes + 2 * vec_bytes + scan_bytes + uv_bytes + partial_bytes; }
 };
 
 static AffineBackwardPlan plan_affine_backward(long long T, int d, long long batch, int dtype, const goom_scan_opts *opts)
@@ -1140,11 +1140,11 @@ static AffineBackwardPlan plan_affine_backward(long long T, int d, long long bat
     p.nsplit = 1;
     p.uv_bytes = p.partial_bytes = 0;
     if (p.one_matrix) {
-        // about a thousand workgroups, at least 64 steps each
-        long long want = (1024 + batch - 1) / batch, most = (T + 63) / 64;
+        // several thousand workgroups (each step's loads depend on one another: many waves in flight hide them), at least 64 steps each
+        long long want = (8192 + batch - 1) / batch, most = (T + 63) / 64;
         p.nsplit = (int)(want < 1 ? 1 : want > most ? most : want);
         const int dp = d <= 16 ? 16 : d <= 32 ? 32 : d <= 64 ? 64 : 128;
-        p.uv_bytes = align_up((size_t)batch * (size_t)T * d * sizeof(double), 256);
+        p.uv_bytes = align_up((size_t)batch * 2 * d * sizeof(double), 256); // u and v of step 0, for the initial state's gradient
         p.partial_bytes = align_up((size_t)batch * p.nsplit * dp * dp * sizeof(double), 256);
     }
     return p;
@@ -1192,7 +1192,7 @@ int goom_affine_scan_backward(goom_ctx *ctx, const void *A, const void *bias, co
         ctx->prof_keep = false;
         if (st) return st;
         unsigned char *U = w + p.at_bytes + 2 * p.vec_bytes + p.scan_bytes;
-        return launch_affine_backward_gradients_one_matrix(ctx, A, bias, h0, H, mu, grad_A, grad_bias, grad_h0, U, U + p.uv_bytes, U + 2 * p.uv_bytes, p.nsplit, T, d,
+        return launch_affine_backward_gradients_one_matrix(ctx, A, bias, h0, H, mu, grad_A, grad_bias, grad_h0, U, U + p.uv_bytes, p.nsplit, T, d,
                                                            batch, dtype);
     }
     // operands of the adjoint recurrence (transposed matrices in reverse time, G / h as GOOMs) ...
@@ -1209,7 +1209,7 @@ int goom_affine_scan_backward(goom_ctx *ctx, const void *A, const void *bias, co
     // ... and the gradients
     if (p.one_matrix) {
         unsigned char *U = w + p.at_bytes + 2 * p.vec_bytes + p.scan_bytes;
-        return launch_affine_backward_gradients_one_matrix(ctx, A, bias, h0, H, mu, grad_A, grad_bias, grad_h0, U, U + p.uv_bytes, U + 2 * p.uv_bytes, p.nsplit, T, d,
+        return launch_affine_backward_gradients_one_matrix(ctx, A, bias, h0, H, mu, grad_A, grad_bias, grad_h0, U, U + p.uv_bytes, p.nsplit, T, d,
                                                            batch, dtype);
     }
     return launch_affine_backward_gradients(ctx, A, bias, h0, H, mu, grad_A, grad_bias, grad_h0, T, d, batch, dtype);

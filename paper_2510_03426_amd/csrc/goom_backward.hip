@@ -39,6 +39,12 @@ template <typename R> __device__ inline double exp_for(double s)
     if (sizeof(R) == 4) return (double)__builtin_amdgcn_exp2f((float)(s * 1.44269504088896340736));
     return exp(s);
 }
+// log of a positive real to the accuracy of the result type
+template <typename R> __device__ inline double log_for(double g)
+{
+    if (sizeof(R) == 4) return (double)__builtin_logf((float)g);
+    return log(g);
+}
 template <typename R> __device__ inline R pi_of() { return sizeof(R) == 4 ? (R)3.14159274101257324219f : (R)3.14159265358979311600; }
 
 // ---- codecs -----------------------------------------------------------------------------------------------
@@ -192,7 +198,7 @@ template <typename R> __global__ __launch_bounds__(256) void bwd_shift_kernel(co
         return finite ? (R)__builtin_rint((double)top) : (R)0;
     };
     const R ct = scale_of(t);
-    const R cnext = scale_of(t + 1);
+    const R cnext = absolute ? (R)0 : scale_of(t + 1); // (uniform: a kernel argument)
     if (!active) return;
     if (sub == 0) shift[b * T + s] = absolute ? (float)ct : s == 0 ? (float)ninf : (float)(ct - cnext);
     for (int i = sub; i < d; i += group) {
@@ -200,7 +206,7 @@ template <typename R> __global__ __launch_bounds__(256) void bwd_shift_kernel(co
         const c2 h = H[(size_t)(b * T + t) * d + i];
         c2 o;
         const bool live = gv != (R)0 && h.x > ninf;
-        o.x = live ? (R)(log(__builtin_fabs((double)gv)) - ((double)h.x - (double)ct)) : ninf;
+        o.x = live ? (R)(log_for<R>(__builtin_fabs((double)gv)) - ((double)h.x - (double)ct)) : ninf;
         o.y = (live && ((gv < (R)0) != odd_phase<R>(h.y))) ? pi_of<R>() : (R)0;
         gt[(size_t)(b * T + s) * d + i] = o;
     }
@@ -218,8 +224,7 @@ template <typename R> __global__ __launch_bounds__(kGradWaves * 64) void bwd_gra
                                                                                          const typename C2<R>::type *__restrict__ h0,
                                                                                          const typename C2<R>::type *__restrict__ H,
                                                                                          const typename C2<R>::type *__restrict__ mu, R *__restrict__ gA,
-                                                                                         R *__restrict__ gb, long long T, int d, long long nsteps,
-                                                                                         double *__restrict__ U, double *__restrict__ V)
+                                                                                         R *__restrict__ gb, long long T, int d, long long nsteps)
 {
     typedef typename C2<R>::type c2;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -260,26 +265,8 @@ template <typename R> __global__ __launch_bounds__(kGradWaves * 64) void bwd_gra
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    if (U) {
-        // one matrix for all steps: its gradient is A[i, j] sum_t lam_t[i] h_{t-1}[j].  This step's factors as doubles,
-        // u[i] = lam_t[i] e^r and v[j] = h_{t-1}[j] e^(-r), r the largest log-magnitude of h_{t-1} (|v| <= 1; u is of the
-        // size of the gradient's terms)
-        double r = ninf;
-        for (int j = lane; j < d; j += 64) r = pre[j] > r ? pre[j] : r;
-        for (int sft = 32; sft > 0; sft >>= 1) {
-            const double o = __shfl_xor(r, sft, 64);
-            r = o > r ? o : r;
-        }
-        const bool any = r > ninf && r < -ninf;
-        for (int i = lane; i < d; i += 64) {
-            const double u = (any && lre[i] > ninf) ? exp(lre[i] + r) : 0.0;
-            const double v = (any && pre[i] > ninf) ? exp(pre[i] - r) : 0.0;
-            U[(size_t)(b * T + t) * d + i] = lneg[i] ? -u : u;
-            V[(size_t)(b * T + t) * d + i] = pneg[i] ? -v : v;
-        }
-    }
-    const c2 *ap = U ? nullptr : A + (size_t)(b * T + t) * d * d;
-    R *op = U ? nullptr : gA + (size_t)(b * T + t) * d * d;
+    const c2 *ap = A + (size_t)(b * T + t) * d * d;
+    R *op = gA + (size_t)(b * T + t) * d * d;
     auto one = [&](int e, c2 a) {
         const int i = e / d, j = e - i * d;
         const double s = lre[i] + (double)a.x + pre[j];
@@ -288,7 +275,7 @@ template <typename R> __global__ __launch_bounds__(kGradWaves * 64) void bwd_gra
         const bool neg = (lneg[i] ^ pneg[j] ^ (odd_phase<R>(a.y) ? 1 : 0)) != 0;
         return (R)(neg ? -v : v);
     };
-    const int nn = U ? 0 : d * d;
+    const int nn = d * d;
     if (sizeof(R) == 4 && (nn & 1) == 0) {
         // two adjacent entries per lane and pass: one 16-byte load, one 8-byte store
         const float4 *ap4 = reinterpret_cast<const float4 *>(ap);
@@ -325,33 +312,89 @@ template <typename R> __global__ __launch_bounds__(128) void bwd_h0_kernel(const
     }
 }
 
-// One matrix for all steps: partial[b, q] = sum over the steps of split q of u_t v_t^T, DP x DP doubles (rows and columns
-// beyond d are zero).  Eight steps at a time through LDS; a thread owns DP * DP / 256 neighbouring entries of one row.
+// One matrix for all steps: its gradient is A[i, j] sum_t lam_t[i] h_{t-1}[j].  partial[b, q] = sum over the steps of span q of
+// u_t v_t^T, DP x DP doubles (rows and columns beyond d are zero), with u_t[i] = lam_t[i] e^r and v_t[j] = h_{t-1}[j] e^(-r), r the
+// largest log-magnitude of h_{t-1} (|v| <= 1; u is of the size of the gradient's terms).  Eight steps at a time: each of the four
+// waves forms u and v of two steps in LDS (side by side in its two halves when d <= 32) (and writes those steps' bias gradients lam_t[i] b_t[i]), then every thread adds the
+// eight products to its DP * DP / 256 neighbouring entries of one row.  u and v of step 0 are kept for the initial state's gradient.
 constexpr int kOuterSteps = 8;
 
-template <int DP> __global__ __launch_bounds__(256) void bwd_outer_kernel(const double *__restrict__ U, const double *__restrict__ V,
-                                                                          double *__restrict__ partial, long long T, int d, int nsplit)
+template <typename R, int DP> __global__ __launch_bounds__(256) void bwd_outer_kernel(const typename C2<R>::type *__restrict__ bias,
+                                                                                     const typename C2<R>::type *__restrict__ h0,
+                                                                                     const typename C2<R>::type *__restrict__ H,
+                                                                                     const typename C2<R>::type *__restrict__ mu, R *__restrict__ gb,
+                                                                                     double *__restrict__ partial, double *__restrict__ uv0, long long T, int d,
+                                                                                     int nsplit)
 {
+    typedef typename C2<R>::type c2;
     constexpr int EPT = DP * DP / 256;
+    constexpr int GROUP = DP <= 32 ? 32 : 64; // lanes that serve one step: short vectors share a wave two by two
+    constexpr int SPW = 64 / GROUP;
     __shared__ double u[kOuterSteps][DP], v[kOuterSteps][DP];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane % GROUP;
     const long long b = blockIdx.x / nsplit;
     const int q = (int)(blockIdx.x - b * nsplit);
     const long long per = (T + nsplit - 1) / nsplit, t0 = q * per, t1 = t0 + per < T ? t0 + per : T;
-    const int e0 = threadIdx.x * EPT, i = e0 / DP, j0 = e0 - i * DP;
+    const int e0 = threadIdx.x * EPT, row = e0 / DP, j0 = e0 - row * DP;
+    const double ninf = -__builtin_huge_val();
     double acc[EPT];
 #pragma unroll
     for (int k = 0; k < EPT; ++k) acc[k] = 0.0;
     for (long long tb = t0; tb < t1; tb += kOuterSteps) {
-        for (int x = threadIdx.x; x < kOuterSteps * DP; x += 256) {
-            const int kb = x / DP, c = x - kb * DP;
-            const bool in = tb + kb < t1 && c < d;
-            u[kb][c] = in ? U[(size_t)(b * T + tb + kb) * d + c] : 0.0;
-            v[kb][c] = in ? V[(size_t)(b * T + tb + kb) * d + c] : 0.0;
+        for (int kb0 = wave * SPW; kb0 < kOuterSteps; kb0 += 4 * SPW) {
+            const int kb = kb0 + lane / GROUP;
+            const long long t = tb + kb;
+            const bool in = t < t1; // the same in all lanes of a group
+            // c_t: the whole number nearest the largest log-magnitude of h_t; r: the largest log-magnitude of h_{t-1}
+            double top = ninf, r = ninf;
+            const c2 *prev = !in ? nullptr : t > 0 ? H + (size_t)(b * T + t - 1) * d : h0 ? h0 + (size_t)b * d : nullptr;
+            for (int i = sub; i < d && in; i += GROUP) {
+                const double hv = (double)H[(size_t)(b * T + t) * d + i].x;
+                top = hv > top ? hv : top;
+                if (prev) {
+                    const double pv = (double)prev[i].x;
+                    r = pv > r ? pv : r;
+                }
+            }
+            for (int sft = GROUP / 2; sft > 0; sft >>= 1) {
+                const double o1 = __shfl_xor(top, sft, 64), o2 = __shfl_xor(r, sft, 64);
+                top = o1 > top ? o1 : top;
+                r = o2 > r ? o2 : r;
+            }
+            const double ct = (top > ninf && top < -ninf) ? __builtin_rint(top) : 0.0;
+            const bool any = r > ninf && r < -ninf;
+            for (int i = sub; i < DP; i += GROUP) {
+                double uu = 0.0, vv = 0.0;
+                if (in && i < d) {
+                    const c2 l = mu[(size_t)(b * T + (T - 1 - t)) * d + i];
+                    const double lre = (double)l.x - ct; // log-magnitude of lam_t[i]; -inf stays -inf
+                    const bool lneg = odd_phase<R>(l.y);
+                    if (any && lre > ninf) uu = exp_for<R>(lre + r); // (float GOOMs: the hardware exponential of the small double sum)
+                    if (lneg) uu = -uu;
+                    if (prev) {
+                        const c2 p = prev[i];
+                        if (any && (double)p.x > ninf) vv = exp_for<R>((double)p.x - r);
+                        if (odd_phase<R>(p.y)) vv = -vv;
+                    }
+                    if (gb) {
+                        const c2 bb = bias[(size_t)(b * T + t) * d + i];
+                        const bool live = lre > ninf && (double)bb.x > ninf;
+                        const double g = live ? exp_for<R>(lre + (double)bb.x) : 0.0;
+                        gb[(size_t)(b * T + t) * d + i] = (R)(lneg != odd_phase<R>(bb.y) ? -g : g);
+                    }
+                    if (t == 0) {
+                        uv0[((size_t)b * 2) * d + i] = uu;
+                        uv0[((size_t)b * 2 + 1) * d + i] = vv;
+                    }
+                }
+                u[kb][i] = uu;
+                v[kb][i] = vv;
+            }
         }
         __syncthreads();
 #pragma unroll
         for (int kb = 0; kb < kOuterSteps; ++kb) {
-            const double ui = u[kb][i];
+            const double ui = u[kb][row];
 #pragma unroll
             for (int k = 0; k < EPT; ++k) acc[k] += ui * v[kb][j0 + k];
         }
@@ -362,10 +405,10 @@ template <int DP> __global__ __launch_bounds__(256) void bwd_outer_kernel(const 
     for (int k = 0; k < EPT; ++k) out[k] = acc[k];
 }
 
-// gA[b, i, j] = A[b, i, j] sum_q partial[b, q, i, j] (in the order of q);  gh0[b, j] = v_0[j] sum_i u_0[i] A[b, i, j]
+// gA[b, i, j] = A[b, i, j] sum_q partial[b, q, i, j] (in the order of q);  gh0[b, j] = v_0[j] sum_i u_0[i] A[b, i, j]  (uv0[b] = u_0, v_0)
 template <typename R> __global__ __launch_bounds__(256) void bwd_outer_finish_kernel(const typename C2<R>::type *__restrict__ A, const double *__restrict__ partial,
-                                                                                     const double *__restrict__ U, const double *__restrict__ V,
-                                                                                     R *__restrict__ gA, R *__restrict__ gh0, long long T, int d, int dp, int nsplit)
+                                                                                     const double *__restrict__ uv0, R *__restrict__ gA,
+                                                                                     R *__restrict__ gh0, int d, int dp, int nsplit)
 {
     typedef typename C2<R>::type c2;
     const long long b = blockIdx.x;
@@ -384,11 +427,11 @@ template <typename R> __global__ __launch_bounds__(256) void bwd_outer_finish_ke
             double acc = 0.0;
             for (int i = 0; i < d; ++i) {
                 const c2 a = A[(size_t)b * d * d + (size_t)i * d + j];
-                const double ui = U[(size_t)b * T * d + i];
+                const double ui = uv0[((size_t)b * 2) * d + i];
                 const double mag = (ui != 0.0 && (double)a.x > ninf) ? exp((double)a.x + log(__builtin_fabs(ui))) : 0.0;
                 acc += (ui < 0.0) != odd_phase<R>(a.y) ? -mag : mag;
             }
-            gh0[(size_t)b * d + j] = (R)(acc * V[(size_t)b * T * d + j]);
+            gh0[(size_t)b * d + j] = (R)(acc * uv0[((size_t)b * 2 + 1) * d + j]);
         }
 }
 
@@ -507,8 +550,7 @@ template <typename R> static int bwd_grad_t(goom_ctx *ctx, const void *A, const 
     prof_begin(ctx, "affine_backward_gradients");
     hipLaunchKernelGGL(bwd_grad_kernel<R>, dim3((unsigned)((nsteps + kGradWaves - 1) / kGradWaves)), dim3(kGradWaves * 64), lds, ctx->stream,
                        static_cast<const c2 *>(A), static_cast<const c2 *>(bias), static_cast<const c2 *>(h0), static_cast<const c2 *>(H),
-                       static_cast<const c2 *>(mu), static_cast<R *>(gA), static_cast<R *>(gb), T, d, nsteps, static_cast<double *>(nullptr),
-                       static_cast<double *>(nullptr));
+                       static_cast<const c2 *>(mu), static_cast<R *>(gA), static_cast<R *>(gb), T, d, nsteps);
     if (gh0) hipLaunchKernelGGL(bwd_h0_kernel<R>, dim3((unsigned)batch), dim3(128), 0, ctx->stream, static_cast<const R *>(gA), static_cast<R *>(gh0), T, d);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch bwd_grad_kernel");
@@ -522,37 +564,33 @@ int launch_affine_backward_gradients(goom_ctx *ctx, const void *A, const void *b
                              : bwd_grad_t<double>(ctx, A, bias, h0, H, mu, gA, gb, gh0, T, d, batch);
 }
 
-// One matrix for all steps.  U, V: [batch, T, d] doubles; partial: [batch, nsplit, dp, dp] doubles (dp: d padded to 16, 32, 64 or 128)
+// One matrix for all steps.  partial: [batch, nsplit, dp, dp] doubles (dp: d padded to 16, 32, 64 or 128); uv0: [batch, 2, d] doubles
 template <typename R> static int bwd_grad_ti_t(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA, void *gb,
-                                               void *gh0, double *U, double *V, double *partial, int nsplit, long long T, int d, long long batch)
+                                               void *gh0, double *uv0, double *partial, int nsplit, long long T, int d, long long batch)
 {
     typedef typename C2<R>::type c2;
-    const size_t lds = (size_t)kGradWaves * d * (2 * sizeof(double) + 2 * sizeof(int));
-    const long long nsteps = batch * T;
     const int dp = d <= 16 ? 16 : d <= 32 ? 32 : d <= 64 ? 64 : 128;
     prof_begin(ctx, "affine_backward_gradients");
-    hipLaunchKernelGGL(bwd_grad_kernel<R>, dim3((unsigned)((nsteps + kGradWaves - 1) / kGradWaves)), dim3(kGradWaves * 64), lds, ctx->stream,
-                       static_cast<const c2 *>(nullptr), static_cast<const c2 *>(bias), static_cast<const c2 *>(h0), static_cast<const c2 *>(H),
-                       static_cast<const c2 *>(mu), static_cast<R *>(nullptr), static_cast<R *>(gb), T, d, nsteps, U, V);
     const dim3 grid((unsigned)(batch * nsplit));
-    if (dp == 16) hipLaunchKernelGGL(bwd_outer_kernel<16>, grid, dim3(256), 0, ctx->stream, U, V, partial, T, d, nsplit);
-    else if (dp == 32) hipLaunchKernelGGL(bwd_outer_kernel<32>, grid, dim3(256), 0, ctx->stream, U, V, partial, T, d, nsplit);
-    else if (dp == 64) hipLaunchKernelGGL(bwd_outer_kernel<64>, grid, dim3(256), 0, ctx->stream, U, V, partial, T, d, nsplit);
-    else hipLaunchKernelGGL(bwd_outer_kernel<128>, grid, dim3(256), 0, ctx->stream, U, V, partial, T, d, nsplit);
-    hipLaunchKernelGGL(bwd_outer_finish_kernel<R>, dim3((unsigned)batch), dim3(256), 0, ctx->stream, static_cast<const c2 *>(A), partial, U, V,
-                       static_cast<R *>(gA), static_cast<R *>(gh0), T, d, dp, nsplit);
+    const c2 *bp = static_cast<const c2 *>(bias), *hp = static_cast<const c2 *>(h0), *Hp = static_cast<const c2 *>(H), *mp = static_cast<const c2 *>(mu);
+    R *gbp = static_cast<R *>(gb);
+    if (dp == 16) hipLaunchKernelGGL((bwd_outer_kernel<R, 16>), grid, dim3(256), 0, ctx->stream, bp, hp, Hp, mp, gbp, partial, uv0, T, d, nsplit);
+    else if (dp == 32) hipLaunchKernelGGL((bwd_outer_kernel<R, 32>), grid, dim3(256), 0, ctx->stream, bp, hp, Hp, mp, gbp, partial, uv0, T, d, nsplit);
+    else if (dp == 64) hipLaunchKernelGGL((bwd_outer_kernel<R, 64>), grid, dim3(256), 0, ctx->stream, bp, hp, Hp, mp, gbp, partial, uv0, T, d, nsplit);
+    else hipLaunchKernelGGL((bwd_outer_kernel<R, 128>), grid, dim3(256), 0, ctx->stream, bp, hp, Hp, mp, gbp, partial, uv0, T, d, nsplit);
+    hipLaunchKernelGGL(bwd_outer_finish_kernel<R>, dim3((unsigned)batch), dim3(256), 0, ctx->stream, static_cast<const c2 *>(A), partial, uv0, static_cast<R *>(gA),
+                       static_cast<R *>(gh0), d, dp, nsplit);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch bwd_outer_kernel");
 }
 
 int launch_affine_backward_gradients_one_matrix(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
-                                                void *gb, void *gh0, void *U, void *V, void *partial, int nsplit, long long T, int d, long long batch, int dtype)
+                                                void *gb, void *gh0, void *uv0, void *partial, int nsplit, long long T, int d, long long batch, int dtype)
 {
     if (batch * T > 0x7fffffffLL || batch * nsplit > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
-    return dtype == GOOM_C64 ? bwd_grad_ti_t<float>(ctx, A, bias, h0, H, mu, gA, gb, gh0, static_cast<double *>(U), static_cast<double *>(V),
-                                                    static_cast<double *>(partial), nsplit, T, d, batch)
-                             : bwd_grad_ti_t<double>(ctx, A, bias, h0, H, mu, gA, gb, gh0, static_cast<double *>(U), static_cast<double *>(V),
-                                                     static_cast<double *>(partial), nsplit, T, d, batch);
+    return dtype == GOOM_C64 ? bwd_grad_ti_t<float>(ctx, A, bias, h0, H, mu, gA, gb, gh0, static_cast<double *>(uv0), static_cast<double *>(partial), nsplit, T, d, batch)
+                             : bwd_grad_ti_t<double>(ctx, A, bias, h0, H, mu, gA, gb, gh0, static_cast<double *>(uv0), static_cast<double *>(partial), nsplit, T, d,
+                                                     batch);
 }
 
 } // namespace goom

@@ -182,9 +182,9 @@ int launch_scan_backward_gradients(goom_ctx *ctx, const void *M, const void *S0,
                                    int d, int m, long long batch, int dtype);
 int launch_affine_backward_prepare_one_matrix(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, float *shift, void *gt, long long T, int d,
                                               long long batch, int dtype); // At [batch, d, d] = A^T; shift[b, s] = c_{T-1-s}
-// one matrix for all steps: gA [batch, d, d]; U, V [batch, T, d] doubles, partial [batch, nsplit, dp, dp] doubles (dp = d padded to 16, 32, 64, 128)
+// one matrix for all steps: gA [batch, d, d]; uv0 [batch, 2, d] doubles, partial [batch, nsplit, dp, dp] doubles (dp = d padded to 16, 32, 64, 128)
 int launch_affine_backward_gradients_one_matrix(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
-                                                void *gb, void *gh0, void *U, void *V, void *partial, int nsplit, long long T, int d, long long batch, int dtype);
+                                                void *gb, void *gh0, void *uv0, void *partial, int nsplit, long long T, int d, long long batch, int dtype);
 int launch_widen_goom(goom_ctx *ctx, const void *z64, void *z128, size_t n); // complex64 GOOMs -> complex128 GOOMs
 int launch_count_nonfinite(goom_ctx *ctx, const void *z, size_t n, int dtype, unsigned long long *count);
 int launch_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, size_t nvec, int d, int dtype);
