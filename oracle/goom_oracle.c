@@ -822,6 +822,23 @@ ORACLE_API void oracle_scaled_exp(const double *re, const uint8_t *sg, double *s
     }
 }
 
+/* Backward of the scaled exponentiation: the log-scaling constant c is computed without altering gradients (Section 4.3:
+ * detached), so scaled_i = (+-) exp(re_i - c + 2) depends on re_i alone with d scaled_i / d re_i = scaled_i, also for the
+ * entry that sets c.  g: gradients with respect to the scaled values; gre: with respect to the log-magnitudes. */
+ORACLE_API void oracle_scaled_exp_backward(const double *re, const uint8_t *sg, const double *g, double *gre, long n, int d)
+{
+    for (long v = 0; v < n; ++v) {
+        const double *r = re + (size_t)v * d;
+        double m = -INFINITY;
+        for (int i = 0; i < d; ++i)
+            if (r[i] > m) m = r[i];
+        for (int i = 0; i < d; ++i) {
+            const long double x = (m > -INFINITY) ? expl((long double)r[i] - (long double)m + 2.0L) : 0.0L;
+            gre[(size_t)v * d + i] = (double)((long double)g[(size_t)v * d + i] * (sg[(size_t)v * d + i] ? -x : x));
+        }
+    }
+}
+
 /* ------------------------------------------------------------------------- */
 /* signed log-add of two GOOM arrays: log(exp(x') + exp(y')) (Section 2, Example 2; */
 /* the bias step of Section 4.3, eq. 26)                                      */

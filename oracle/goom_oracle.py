@@ -480,6 +480,18 @@ def scaled_exp(z):
     return scaled, c
 
 
+def scaled_exp_backward(z, grad_scaled):
+    """Backward of scaled_exp with the log-scaling constant detached (Section 4.3): gradients with respect to Re z."""
+    re, sg = _as_working(z)
+    d = re.shape[-1]
+    n = int(np.prod(re.shape[:-1])) if re.ndim > 1 else 1
+    g = _c(grad_scaled, np.float64)
+    assert g.shape == re.shape
+    out = np.empty(re.shape, dtype=np.float64)
+    lib().oracle_scaled_exp_backward(_p(re), _p(sg), _p(g), _p(out), C.c_long(n), C.c_int(d))
+    return out
+
+
 def log_add_exp(x, y):
     """Elementwise signed log-add of two GOOM arrays: the GOOM of exp(x) + exp(y).  Returns (re, sg)."""
     xre, xsg = _as_working(x)

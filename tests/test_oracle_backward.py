@@ -304,3 +304,23 @@ def test_time_invariant_recurrence_backward(oracle):
     assert none is None and np.array_equal(gAb[1], gA1) and np.array_equal(gbb[1], gb1)
     full, gbf, _, _ = oracle.affine_scan_backward(np.broadcast_to(Ab[:, None], (2, T, d, d)).copy(), bb, Gb)
     assert np.allclose(gAb, full.sum(axis=1), rtol=1e-13) and np.array_equal(gbb, gbf)
+
+
+def test_scaled_exp_backward_constant_detached(oracle):
+    # Section 4.3: c = max Re z takes no gradient.  With c held at its value, scaled_i = +-exp(re_i - c + 2) and the derivative
+    # with respect to re_i is scaled_i itself, also for the entry that sets c (were c differentiated, that entry's would be 0)
+    rng = np.random.default_rng(71)
+    z = goom_of(rng.standard_normal((3, 6)) * np.exp(rng.uniform(-5, 5, (3, 6)))) + np.array([[900.0], [-4000.0], [0.0]])
+    g = rng.standard_normal((3, 6))
+    got = oracle.scaled_exp_backward(z, g)
+    scaled, c = oracle.scaled_exp(z)
+    assert np.allclose(got, g * scaled, rtol=1e-15)
+    top = np.argmax(z.real, axis=1)
+    assert np.allclose(got[np.arange(3), top], g[np.arange(3), top] * np.where(z.imag[np.arange(3), top] != 0, -1, 1) * math.exp(2.0), rtol=1e-14)
+    delta = 1e-6
+    for (v, i) in [(0, 0), (1, 3), (2, 5), (0, int(top[0]))]:
+        f = lambda r: math.exp(r - c[v] + 2.0) * (-1.0 if z.imag[v, i] != 0 else 1.0)  # c fixed
+        fd = g[v, i] * (f(z.real[v, i] + delta) - f(z.real[v, i] - delta)) / (2 * delta)
+        assert abs(got[v, i] - fd) < 1e-8 * max(1.0, abs(fd))
+    # a vector of zeros passes nothing
+    assert np.all(oracle.scaled_exp_backward(np.full((1, 4), -np.inf + 0j), np.ones((1, 4))) == 0)
