@@ -375,6 +375,13 @@ int goom_to_goom_backward(goom_ctx *ctx, const void *x, const void *grad_re, voi
 int goom_from_goom_backward(goom_ctx *ctx, const void *y, const void *grad_x, void *grad_re, size_t n, int dtype,
                             double eps);
 
+/* Backward of goom_scaled_exp and of the scaled states of goom_affine_scan_scaled (paper Section 4.3): the log-scaling
+ * constant c = max Re z is computed without altering gradients, so scaled[i] = +-exp(Re z[i] - c + 2) has
+ * d scaled[i] / d Re z[i] = scaled[i], also for the entry that sets c: grad_re[i] = grad_scaled[i] * scaled[i].
+ * scaled (as returned by the forward call), grad_scaled, grad_re: n reals of the component type (device). */
+int goom_scaled_exp_backward(goom_ctx *ctx, const void *scaled, const void *grad_scaled, void *grad_re, size_t n,
+                             int dtype);
+
 /* Backward of goom_lmme (paper Section 3.2 with the derivatives of Section 3.1 in the limit eps -> 0, as for the
  * recurrence below).  With C = A B over reals and grad_C[b, i, k] = dL / d Re C'[b, i, k] for some loss L,
  *     grad_A[b, i, j] = dL / d Re A'[b, i, j] = A_ij sum_k (grad_C_ik / C_ik) B_jk,

@@ -31,7 +31,7 @@ EXPORTS = [
     "goom_affine_scan", "goom_affine_scan_workspace_bytes", "goom_affine_scan_scaled",
     "goom_affine_scan_scaled_workspace_bytes", "goom_scaled_exp", "goom_log_add_exp",
     "goom_count_nonfinite", "goom_to_goom_backward", "goom_from_goom_backward", "goom_affine_scan_backward", "goom_affine_scan_backward_workspace_bytes",
-    "goom_lmme_backward", "goom_lmme_backward_workspace_bytes", "goom_scan_backward", "goom_scan_backward_workspace_bytes",
+    "goom_lmme_backward", "goom_lmme_backward_workspace_bytes", "goom_scan_backward", "goom_scan_backward_workspace_bytes", "goom_scaled_exp_backward",
 ]
 
 
@@ -126,6 +126,7 @@ def load_library():
     lib.goom_lmme_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, u32, vp, sz]
     lib.goom_lmme_backward_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, u32]
     lib.goom_lmme_backward_workspace_bytes.restype = sz
+    lib.goom_scaled_exp_backward.argtypes = [vp, vp, vp, vp, sz, i32]
     lib.goom_scan_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i64, i32, po, vp, sz]
     lib.goom_scan_backward_workspace_bytes.argtypes = [i64, i32, i32, i64, i32, po, i32]
     lib.goom_scan_backward_workspace_bytes.restype = sz
@@ -551,6 +552,13 @@ class Goom:
         c = torch.empty(z.shape[:-1], dtype=comp, device=z.device) if want_logscale else None
         self._check(self.lib.goom_scaled_exp(self._ctx, _ptr(z), _ptr(out), _ptr(c), nvec, d, code))
         return (out, c) if want_logscale else out
+
+    def scaled_exp_backward(self, scaled, grad_scaled):
+        """Gradient with respect to Re z of scaled = scaled_exp(z), the log-scaling constant detached."""
+        assert scaled.shape == grad_scaled.shape and scaled.dtype == grad_scaled.dtype
+        out = self.torch.empty_like(scaled)
+        self._check(self.lib.goom_scaled_exp_backward(self._ctx, _ptr(scaled), _ptr(grad_scaled), _ptr(out), scaled.numel(), _dtype_code(scaled)))
+        return out
 
     def log_add_exp(self, x, y, out=None):
         """Elementwise GOOM of exp(x) + exp(y)."""

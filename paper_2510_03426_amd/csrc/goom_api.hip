@@ -1468,6 +1468,17 @@ int goom_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, 
     return launch_scaled_exp(ctx, z, scaled, logscale, n_vectors, d, dtype);
 }
 
+int goom_scaled_exp_backward(goom_ctx *ctx, const void *scaled, const void *grad_scaled, void *grad_re, size_t n, int dtype)
+{
+    if (int s = check_common(ctx, dtype)) return s;
+    if (n == 0) return ctx ? GOOM_OK : fail(nullptr, GOOM_EINVAL, "null context");
+    if (!scaled || !grad_scaled || !grad_re) return fail(ctx, GOOM_EINVAL, "null data pointer");
+    const size_t al = comp_bytes(dtype);
+    if (!aligned(scaled, al) || !aligned(grad_scaled, al) || !aligned(grad_re, al)) return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
+    if (int s = need_ctx(ctx)) return s;
+    return launch_scaled_exp_backward(ctx, scaled, grad_scaled, grad_re, n, dtype);
+}
+
 size_t goom_lyapunov_spectrum_per_step_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_reset_opts *opts,
                                                        int caller_has_states, int caller_has_step_logs)
 {

@@ -71,6 +71,15 @@ template <typename R> __global__ __launch_bounds__(256) void from_goom_backward_
     }
 }
 
+// scaled exponentiation (Section 4.3): the log-scaling constant takes no gradient, so the gradient with respect to the
+// log-magnitude is the scaled value times the gradient with respect to it
+template <typename R> __global__ __launch_bounds__(256) void scaled_exp_backward_kernel(const R *__restrict__ scaled, const R *__restrict__ g, R *__restrict__ gre,
+                                                                                        size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) gre[i] = scaled[i] * g[i];
+}
+
 // ---- recurrence -------------------------------------------------------------------------------------------
 // Operands of the adjoint recurrence, indexed by s = T - 1 - t:
 //   At[b, s] = A[b, T - s]^T for s >= 1 (the matrix for s = 0 multiplies the zero initial adjoint: written as zeros),
@@ -457,6 +466,20 @@ int launch_to_goom_backward(goom_ctx *ctx, const void *x, const void *g, void *g
                            static_cast<const double *>(g), static_cast<double *>(gx), n, eps);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch to_goom_backward");
+}
+
+int launch_scaled_exp_backward(goom_ctx *ctx, const void *scaled, const void *g, void *gre, size_t n, int dtype)
+{
+    if (n == 0) return GOOM_OK;
+    prof_begin(ctx, "scaled_exp_backward");
+    if (dtype == GOOM_C64)
+        hipLaunchKernelGGL(scaled_exp_backward_kernel<float>, dim3(blocks_for(n)), dim3(256), 0, ctx->stream, static_cast<const float *>(scaled),
+                           static_cast<const float *>(g), static_cast<float *>(gre), n);
+    else
+        hipLaunchKernelGGL(scaled_exp_backward_kernel<double>, dim3(blocks_for(n)), dim3(256), 0, ctx->stream, static_cast<const double *>(scaled),
+                           static_cast<const double *>(g), static_cast<double *>(gre), n);
+    prof_end(ctx);
+    return check_hip(ctx, hipGetLastError(), "launch scaled_exp_backward");
 }
 
 int launch_from_goom_backward(goom_ctx *ctx, const void *y, const void *gx, void *g, size_t n, int dtype, double eps)

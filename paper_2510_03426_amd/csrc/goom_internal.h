@@ -162,6 +162,7 @@ int launch_probe(goom_ctx *ctx, const void *a, void *b, size_t bytes, int mode);
 int launch_matrix_probe(goom_ctx *ctx, void *sink, long long iters, int dtype);
 // backward passes (goom_backward.hip)
 int launch_to_goom_backward(goom_ctx *ctx, const void *x, const void *g, void *gx, size_t n, int dtype, double eps);
+int launch_scaled_exp_backward(goom_ctx *ctx, const void *scaled, const void *g, void *gre, size_t n, int dtype);
 int launch_from_goom_backward(goom_ctx *ctx, const void *y, const void *gx, void *g, size_t n, int dtype, double eps);
 int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, float *shift, void *gt, long long T, int d,
                                    long long batch, int dtype, bool one_matrix = false); // one_matrix: A is [batch, d, d], every step's factor

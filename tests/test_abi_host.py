@@ -78,6 +78,7 @@ def test_argument_validation_without_device(lib):
     assert lib.goom_affine_scan_backward(None, p, p, None, p, p, p, p, p, 64, 8, 1, 0, None, None, 0) == EINVAL and "initial" in err(lib)
     assert lib.goom_affine_scan_backward(None, p, p, None, p, p, p, p, None, 64, 8, 1, 0, None, None, 0) == EWS
     assert lib.goom_affine_scan_backward_workspace_bytes(64, 8, 1, 0, None) > 64 * 8 * 8 * 8
+    assert lib.goom_scaled_exp_backward(None, p, None, p, 16, 0) == EINVAL
     assert lib.goom_lmme_backward(None, p, p, p, None, p, p, 2, 8, 8, 8, 0, 0, None, 0) == EINVAL
     assert lib.goom_lmme_backward(None, p, p, p, p, p, p, 2, 8, 2000, 8, 0, 0, None, 0) == EUNSUP
     assert lib.goom_lmme_backward(None, p, p, p, p, p, p, 2, 8, 8, 8, 0, 4, None, 0) == EINVAL and "flags" in err(lib)

@@ -1041,6 +1041,26 @@ def test_affine_scan_backward_time_invariant(G, oracle, T, d, batch, chunk, ctyp
 
 
 @pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
+def test_scaled_exp_backward(G, oracle, ctype):
+    # the states' scaled exponentials and their gradient with the log-scaling constant detached (Section 4.3)
+    comp = np.float32 if ctype == np.complex64 else np.float64
+    rng = np.random.default_rng(81)
+    n, d = 1000, 32
+    z = oracle.to_goom(si.normal_f32(si.BASE_SEED + 121, 3, n * d).reshape(n, d).astype(comp))
+    z.real += rng.uniform(-3000, 3000, (n, 1)).astype(comp)
+    z[5, :] = -np.inf  # a vector of zeros
+    g = si.normal_f32(si.BASE_SEED + 122, 4, n * d).reshape(n, d).astype(comp)
+    scaled = G.scaled_exp(dev(z))
+    got = host(G.scaled_exp_backward(scaled, dev(g))).astype(np.float64)
+    want = oracle.scaled_exp_backward(z, g)
+    rel = 4e-6 if comp == np.float32 else 1e-13  # (the forward values carry their own rounding; the product adds half a unit)
+    assert np.all(np.abs(got - want) <= rel * np.abs(want) + 1e-30)
+    assert np.all(got[5] == 0)
+    top = np.argmax(z.real[0])
+    assert abs(abs(got[0, top]) - abs(float(g[0, top])) * math.exp(2.0)) <= 1e-5 * abs(float(g[0, top])) * math.exp(2.0)  # the entry that sets c passes its gradient
+
+
+@pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
 def test_signed_log_add(G, oracle, ctype):
     comp = np.float32 if ctype == np.complex64 else np.float64
     rng = np.random.default_rng(78)
