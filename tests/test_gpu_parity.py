@@ -1060,6 +1060,52 @@ def test_scaled_exp_backward(G, oracle, ctype):
     assert abs(abs(got[0, top]) - abs(float(g[0, top])) * math.exp(2.0)) <= 1e-5 * abs(float(g[0, top])) * math.exp(2.0)  # the entry that sets c passes its gradient
 
 
+@pytest.mark.parametrize("ctype,T,d,chunk", [(np.complex128, 64, 16, 8), (np.complex64, 400, 16, 16), (np.complex64, 300, 32, 0), (np.complex64, 50, 24, 0)])
+def test_state_space_layer_forward_and_backward(G, oracle, ctype, T, d, chunk):
+    """The recurrent core of the paper's layer (Section 4.3) end to end through the library's calls, forward and backward:
+    bias_t = B u_t (an LMME), x_t = A x_{t-1} + bias_t with one matrix for all steps, scaled x_t = exp(x'_t - c + 2) with c
+    detached; loss = sum w * scaled.  Every stage against the oracle's, fed the device's forward values."""
+    comp = np.float32 if ctype == np.complex64 else np.float64
+    batch = 2
+    A, _ = si.recurrence_inputs(si.BASE_SEED + 131, batch, 1, d, gain=1.03)
+    Az = oracle.to_goom(A[:, 0].astype(comp))
+    Bz = oracle.to_goom((si.normal_f32(si.BASE_SEED + 132, 5, batch * d * d).reshape(batch, d, d) / math.sqrt(d)).astype(comp))
+    Uz = oracle.to_goom(si.normal_f32(si.BASE_SEED + 133, 6, batch * T * d).reshape(batch, T, d).astype(comp))
+    x0 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 134, 7, batch * d).reshape(batch, d).astype(comp))
+    w = si.normal_f32(si.BASE_SEED + 135, 8, batch * T * d).reshape(batch, T, d).astype(comp)
+    say(f"state-space layer T={T} d={d} {np.dtype(ctype).name} chunk={chunk}")
+    # forward: rows u_t times B^T
+    Btz = np.ascontiguousarray(np.swapaxes(Bz, -1, -2))
+    bias_d = G.lmme(dev(Uz), dev(Btz))
+    x_d = G.affine_scan(dev(Az), bias_d, dev(x0), chunk_len=chunk, time_invariant=True)
+    scaled_d = G.scaled_exp(x_d)
+    # backward
+    gx_d = G.scaled_exp_backward(scaled_d, dev(w))
+    gA, gbias_d, gx0 = G.affine_scan_backward(dev(Az), bias_d, x_d, gx_d, dev(x0), chunk_len=chunk, time_invariant=True)
+    gU, gBt = G.lmme_backward(dev(Uz), dev(Btz), bias_d, gbias_d)
+    # the oracle's stages on the device's forward values
+    bias, x, scaled, gx, gbias = host(bias_d), host(x_d), host(scaled_d), host(gx_d).astype(np.float64), host(gbias_d).astype(np.float64)
+    rel = 5e-5 if comp == np.float32 else 1e-11
+    want_gx = oracle.scaled_exp_backward(x, w)
+    assert np.all(np.abs(gx - want_gx) <= 1e-5 * np.abs(want_gx) + 1e-30)
+    rep = np.ascontiguousarray(np.broadcast_to(Az[:, None], (batch, T, d, d)))
+    per_step, want_gb, want_gx0, _ = oracle.affine_scan_backward(rep, bias, gx, h0=x0, h=x)
+    mass = np.abs(per_step).sum(axis=1)
+    err_a = np.abs(host(gA).astype(np.float64) - per_step.sum(axis=1)) / (rel * mass + 1e-30)
+    err_b = np.abs(gbias - want_gb) / (rel * np.abs(want_gb) + rel * np.abs(want_gb).max(axis=-1, keepdims=True) + 1e-30)
+    want_gU, want_gBt = oracle.lmme_backward(Uz, Btz, gbias, c=bias)
+    mU, mBt = oracle.lmme_backward(Uz.real + 0j, Btz.real + 0j, np.abs(gbias), c=bias.real + 0j)
+    lrel = 1e-5 if comp == np.float32 else 1e-11
+    err_u = np.abs(host(gU).astype(np.float64) - want_gU) / (lrel * mU + 1e-30)
+    err_bt = np.abs(host(gBt).astype(np.float64) - want_gBt) / (lrel * mBt + 1e-30)
+    say(f"  worst error / tolerance: grad A {err_a.max():.3g}, grad bias {np.median(err_b):.3g} (median) {err_b.max():.3g} (max), "
+        f"grad u {err_u.max():.3g}, grad B {err_bt.max():.3g}")
+    assert err_a.max() <= 1 and err_u.max() <= 1 and err_bt.max() <= 1
+    assert err_b.max() <= 1  # (a contracting or mildly expanding matrix: the adjoints' sums do not cancel; the recurrence's own test covers those that do)
+    assert np.all(np.abs(host(gx0).astype(np.float64) - want_gx0) <= 5 * rel * np.abs(want_gx0) + 1e-2 * rel * np.abs(want_gx0).max())
+    assert host(gBt).shape == (batch, d, d) and host(gA).shape == (batch, d, d)
+
+
 @pytest.mark.parametrize("ctype", [np.complex64, np.complex128])
 def test_signed_log_add(G, oracle, ctype):
     comp = np.float32 if ctype == np.complex64 else np.float64
