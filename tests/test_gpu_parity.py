@@ -936,7 +936,7 @@ def test_lmme_backward(G, oracle, shape, ctype, flags, spread):
     (40, 8, 8, 2, 0, np.complex64, False), (300, 16, 16, 2, 16, np.complex64, True), (257, 32, 8, 1, 0, np.complex64, True),
     (60, 64, 64, 1, 0, np.complex64, False), (60, 24, 40, 2, 7, np.complex128, True), (1, 16, 16, 2, 0, np.complex64, True),
     (30, 100, 60, 1, 0, np.complex64, True), (2000, 16, 16, 1, 0, np.complex64, False), (1, 8, 8, 1, 0, np.complex128, False),
-    (500, 12, 5, 3, 50, np.complex64, True)])
+    (500, 12, 5, 3, 50, np.complex64, True), (12, 200, 100, 1, 0, np.complex64, True), (10, 136, 136, 1, 4, np.complex128, False)])
 def test_scan_backward(G, oracle, T, d, m, batch, chunk, ctype, with_init):
     """Gradients of L = sum grad_p * Re p with respect to the log-magnitudes of every factor and of the initial state,
     against the oracle's adjoint recurrence fed the same forward states."""
