@@ -1019,7 +1019,42 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
             l.m = d + 1;
             l.bias_col = d;
         }
+        // A^L = (A^L1)^L2 shortens the chain of dependent products from L to L1 + L2 (one wave-sized chain per batch item: its
+        // length is the whole cost).  The inner power goes to the second chunk's slot, which is overwritten afterwards.
+        const long long L1 = (f64 && p.L >= 64 && p.L % 16 == 0) ? (p.L >= 1024 && p.L % 32 == 0 ? 32 : 16) : 0;
+        if (L1) {
+            l.steps = L1;
+            l.chunk_len = L1;
+            l.out_fact_final = totals + p.tot.stride;
+        }
         if (int s = launch_chain(ctx, l)) return s;
+        if (L1) { // the outer power: L2 equal factored factors, as the carry phase multiplies chunk products
+            ChainLaunch o;
+            std::memset(&o, 0, sizeof o);
+            o.dp = p.dp;
+            o.dtype = GOOM_C128;
+            o.n = d;
+            o.d = d;
+            o.m = d + 1;
+            o.batch = batch;
+            o.left_fact = 1;
+            o.left_fact_cols = p.tot.cols_padded;
+            o.left = totals + p.tot.stride;
+            o.left_batch_stride = (long long)p.tot.stride * p.C;
+            o.left_step_stride = 0; // the same factor at every step
+            o.steps = p.L / L1;
+            o.chunk_len = o.steps;
+            o.chunks_launched = 1;
+            o.init_mode = 0;
+            o.bias_mode = 2; // (the factor's bias column is zero, and stays so)
+            o.bias_col = d;
+            o.out_fact_final = totals;
+            o.final_common_exponent = 1;
+            o.fact_stride = (long long)p.tot.stride * p.C;
+            o.fact_cols = p.tot.cols_padded;
+            o.label = "affine_phase1_matrix_power";
+            if (int s = launch_chain(ctx, o)) return s;
+        }
         if (int s = goom_chain::launch_replicate_power(ctx, totals, (long long)p.tot.stride, p.tot.cols_padded, p.dp, d, batch, p.C - 1, p.C, f64 != 0)) return s;
         ChainLaunch w = base;
         w.m = 1;
