@@ -1308,6 +1308,12 @@ int goom_lmme_backward(goom_ctx *ctx, const void *A, const void *B, const void *
     void *X = static_cast<unsigned char *>(Bt) + p.bt_bytes;
     void *Y = static_cast<unsigned char *>(X) + p.x_bytes;
     void *lw = p.lmme_bytes ? static_cast<unsigned char *>(Y) + p.y_bytes : nullptr;
+    if (n == 128 && d == 128 && m == 128 && !(flags & GOOM_LMME_EXACT)) {
+        // the full-size product kernel transposes and shifts its operand as it reads it and exponentiates as it stores
+        if (int s = launch_lmme_backward_prepare128(ctx, A, B, Cm, grad_C, r, c, W, batch, dtype)) return s;
+        if (int s = launch_lmme128_backward(ctx, 1, W, B, A, c, r, grad_A, batch, dtype)) return s;
+        return launch_lmme128_backward(ctx, 2, A, W, B, r, c, grad_B, batch, dtype);
+    }
     // shifts, W~' = GOOM(G) - C~', and the shifted operands transposed ...
     if (int s = launch_lmme_backward_prepare(ctx, A, B, Cm, grad_C, r, c, W, At, Bt, batch, n, d, m, dtype)) return s;
     // ... X~ = W~ B~^T [n, d] and Y~ = A~^T W~ [d, m], by the forward product itself ...

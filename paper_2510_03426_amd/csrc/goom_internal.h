@@ -168,9 +168,13 @@ int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, 
                                    long long batch, int dtype, bool one_matrix = false); // one_matrix: A is [batch, d, d], every step's factor
 int launch_affine_backward_gradients(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
                                      void *gb, void *gh0, long long T, int d, long long batch, int dtype);
+int launch_lmme128_backward(goom_ctx *ctx, int mode, const void *left, const void *right, const void *Z, const void *in_shift, const void *out_shift,
+                            void *grad, long long batch, int dtype); // goom_lmme128.hip: a product of the backward pass with its operand transposed on the fly
 // backward of LMME (goom_lmme_backward.hip): shifts r [batch, n], c [batch, m]; W [batch, n, m], At [batch, d, n], Bt [batch, m, d] GOOMs
 int launch_lmme_backward_prepare(goom_ctx *ctx, const void *A, const void *B, const void *Cm, const void *G, void *r, void *c, void *W, void *At, void *Bt,
                                  long long batch, int n, int d, int m, int dtype);
+int launch_lmme_backward_prepare128(goom_ctx *ctx, const void *A, const void *B, const void *Cm, const void *G, void *r, void *c, void *W, long long batch,
+                                    int dtype); // n = d = m = 128: shifts and W only
 int launch_lmme_backward_finish(goom_ctx *ctx, const void *A, const void *B, const void *X, const void *Y, const void *r, const void *c, void *gA, void *gB,
                                 long long batch, int n, int d, int m, int dtype);
 // backward of the prefix scan (goom_scan_backward.hip): c [batch, T + 1] reals; F [batch, nsteps, d + m, d + m], init [batch, d + m, m],

@@ -31,9 +31,31 @@ struct Lmme128Args {
     const void *A, *B;
     void *C;
     void *shifts; // NULL, or per pair the 128 row shifts n_i then the 128 column shifts e_k (for the repair pass)
+    // backward modes: the addend Z [pair, 128, 128] GOOMs, the shift of the transposed operand's log-magnitudes along the inner
+    // index and that of the addend along the output's rows (MODE 1) or columns (MODE 2), 128 reals per pair each
+    const void *Z, *in_shift, *out_shift;
 };
 
-template <typename R> __global__ __launch_bounds__(kThreads) void lmme_ktile_kernel(Lmme128Args a)
+constexpr double kInvPi = 0.318309886183790671538;
+template <typename R> __device__ inline bool odd_phase(R im)
+{
+    const int k = (int)__builtin_rint((double)im * kInvPi);
+    return (k & 1) != 0;
+}
+template <typename R> __device__ inline double exp_for(double s)
+{
+    if (sizeof(R) == 4) return (double)__builtin_amdgcn_exp2f((float)(s * 1.44269504088896340736));
+    return exp(s);
+}
+
+// MODE 0: C' = LMME(A', B') as GOOMs.
+// MODE 1, 2 (the two products of the backward pass): the result leaves as reals, C[i, k] = +- exp(Re Z'[i, k] - s + Re P'[i, k]),
+// P the product, s = out_shift[i] (MODE 1) or out_shift[k] (MODE 2); and one operand is read transposed from its array with
+// in_shift taken from its log-magnitudes along the inner index:
+//   MODE 1: right operand (j, k) = B[k][j] e^(-in_shift[j])      MODE 2: left operand (i, j) = A[j][i] e^(-in_shift[j])
+// (MODE 1 with float components is held to four waves per SIMD, i.e. 128 registers a lane: two workgroups per compute unit as in the
+// other modes; left alone it takes 156 registers, one workgroup per compute unit, and 1.4 ms in place of 1.1)
+template <typename R, int MODE> __global__ __launch_bounds__(kThreads, (sizeof(R) == 4 && MODE == 1) ? 4 : 1) void lmme_ktile_kernel(Lmme128Args a)
 {
     typedef Comp<R> CR;
     typedef typename CR::vec4 vec4;
@@ -55,7 +77,8 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_ktile_ker
     const long long pair = blockIdx.x;
     const R *Ap = static_cast<const R *>(a.A) + (size_t)pair * kD * kD * 2;
     const R *Bp = static_cast<const R *>(a.B) + (size_t)pair * kD * kD * 2;
-    R *Cp = static_cast<R *>(a.C) + (size_t)pair * kD * kD * 2;
+    R *Cp = static_cast<R *>(a.C) + (size_t)pair * kD * kD * (MODE == 0 ? 2 : 1);
+    [[maybe_unused]] const R *ins = MODE != 0 ? static_cast<const R *>(a.in_shift) + (size_t)pair * kD : nullptr;
     const R kNone = (R)-1.0e30; // "no finite entry seen yet"
 
     // producer side: this thread's rows and column pair inside a tile
@@ -63,9 +86,16 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_ktile_ker
     auto load_a = [&](int q, Item<R> (&it)[QA]) {
 #pragma unroll
         for (int p = 0; p < QA; ++p) {
-            const R *gp = Ap + ((size_t)(prow + p * RPP) * kD + q * kKQ + pcj) * 2;
-            const vec4 w = *reinterpret_cast<const vec4 *>(gp);
-            it[p].re0 = w[0]; it[p].im0 = w[1]; it[p].re1 = w[2]; it[p].im1 = w[3];
+            if (MODE == 2) { // entries (row, k), (row, k + 1) of the transpose: two loads a row of the array apart
+                const int k = q * kKQ + pcj;
+                const R *gp = Ap + ((size_t)k * kD + prow + p * RPP) * 2;
+                it[p].re0 = gp[0] - ins[k]; it[p].im0 = gp[1];
+                it[p].re1 = gp[2 * kD] - ins[k + 1]; it[p].im1 = gp[2 * kD + 1];
+            } else {
+                const R *gp = Ap + ((size_t)(prow + p * RPP) * kD + q * kKQ + pcj) * 2;
+                const vec4 w = *reinterpret_cast<const vec4 *>(gp);
+                it[p].re0 = w[0]; it[p].im0 = w[1]; it[p].re1 = w[2]; it[p].im1 = w[3];
+            }
         }
     };
     // consumer side: rows 32 q + 16 kt + row_of(g, v) of column col
@@ -74,9 +104,18 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_ktile_ker
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const R *gp = Bp + ((size_t)(q * kKQ + 16 * kt + CR::row_of(g, v)) * kD + col) * 2;
-                bre[kt][v] = gp[0];
-                bim[kt][v] = gp[1];
+                // MODE 1: a lane's four inner indices of a 16-tile are neighbours, 4 g + v (32 contiguous bytes of the array's row `col`);
+                // the tile of the left operand is then laid out in plain order (see convert_a)
+                const int k = q * kKQ + 16 * kt + (MODE == 1 ? 4 * g + v : CR::row_of(g, v));
+                if (MODE == 1) { // entry (k, col) of the transpose
+                    const R *gp = Bp + ((size_t)col * kD + k) * 2;
+                    bre[kt][v] = gp[0] - ins[k];
+                    bim[kt][v] = gp[1];
+                } else {
+                    const R *gp = Bp + ((size_t)k * kD + col) * 2;
+                    bre[kt][v] = gp[0];
+                    bim[kt][v] = gp[1];
+                }
             }
     };
 
@@ -95,8 +134,8 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_ktile_ker
             const R nnew = cand > nprev[p] ? cand : nprev[p];
             const R x0 = CR::apply_sign(CR::exp2_shifted(it[p].re0, nnew), it[p].im0);
             const R x1 = CR::apply_sign(CR::exp2_shifted(it[p].re1, nnew), it[p].im1);
-            tile[row * LDQ + CR::phys(pcj)] = x0;
-            tile[row * LDQ + CR::phys(pcj + 1)] = x1;
+            tile[row * LDQ + (MODE == 1 ? pcj : CR::phys(pcj))] = x0;
+            tile[row * LDQ + (MODE == 1 ? pcj + 1 : CR::phys(pcj + 1))] = x1;
             nsh[CR::phys(row)] = nnew;
             dsh[CR::phys(row)] = nprev[p] - nnew; // <= 0; hugely negative the first time a row gets entries
             nprev[p] = nnew;
@@ -173,10 +212,20 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_ktile_ker
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const R x = acc[mt][v];
-            R *op = Cp + ((size_t)(16 * mt + CR::row_of(g, v)) * kD + col) * 2;
-            const bool zero = x == (R)0;
-            op[0] = zero ? CR::neg_inf() : CR::out_re(x, nv[v], (double)ecol);
-            op[1] = x < (R)0 ? CR::pi() : (R)0;
+            const int i = 16 * mt + CR::row_of(g, v);
+            if (MODE == 0) {
+                R *op = Cp + ((size_t)i * kD + col) * 2;
+                const bool zero = x == (R)0;
+                op[0] = zero ? CR::neg_inf() : CR::out_re(x, nv[v], (double)ecol);
+                op[1] = x < (R)0 ? CR::pi() : (R)0;
+            } else {
+                const R *zp = static_cast<const R *>(a.Z) + ((size_t)pair * kD * kD + (size_t)i * kD + col) * 2;
+                const R zre = zp[0], zim = zp[1];
+                const R osh = static_cast<const R *>(a.out_shift)[(size_t)pair * kD + (MODE == 1 ? i : col)];
+                double val = 0.0;
+                if (x != (R)0 && zre != CR::neg_inf()) val = exp_for<R>(((double)zre - (double)osh) + (double)CR::out_re(x, nv[v], (double)ecol));
+                Cp[(size_t)i * kD + col] = (R)((x < (R)0) != odd_phase<R>(zim) ? -val : val);
+            }
         }
     }
     // the final shifts (whole numbers of log2 units; -1e30 for a row or column without a finite entry), by row and column
@@ -187,11 +236,11 @@ template <typename R> __global__ __launch_bounds__(kThreads) void lmme_ktile_ker
     }
 }
 
-template <typename R> int launch_ktile(goom_ctx *ctx, const Lmme128Args &args, long long batch)
+template <typename R, int MODE> int launch_ktile(goom_ctx *ctx, const Lmme128Args &args, long long batch)
 {
     constexpr int LDQ = kKQ + Comp<R>::kPad;
     const size_t lds = 2 * ((size_t)kD * LDQ * sizeof(R) + 2 * (size_t)kD * sizeof(R));
-    auto kern = lmme_ktile_kernel<R>;
+    auto kern = lmme_ktile_kernel<R, MODE>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return goom::check_hip(ctx, e, "hipFuncSetAttribute(lmme_ktile_kernel)");
@@ -209,8 +258,19 @@ namespace goom {
 
 int launch_lmme128(goom_ctx *ctx, const void *A, const void *B, void *C, long long batch, int dtype, void *shifts)
 {
-    Lmme128Args args{A, B, C, shifts};
-    return dtype == GOOM_C64 ? launch_ktile<float>(ctx, args, batch) : launch_ktile<double>(ctx, args, batch);
+    Lmme128Args args{A, B, C, shifts, nullptr, nullptr, nullptr};
+    return dtype == GOOM_C64 ? launch_ktile<float, 0>(ctx, args, batch) : launch_ktile<double, 0>(ctx, args, batch);
+}
+
+// The two products of the backward pass of a 128 x 128 x 128 LMME, their results as real gradients (see the kernel's modes):
+// mode 1: grad[i, j] = +- exp(Re Z'[i, j] - out_shift[i] + log|sum_k left[i, k] right[j, k] e^(-in_shift[k])|)
+// mode 2: grad[j, k] = +- exp(Re Z'[j, k] - out_shift[k] + log|sum_i left[i, j] e^(-in_shift[i]) right[i, k]|)
+int launch_lmme128_backward(goom_ctx *ctx, int mode, const void *left, const void *right, const void *Z, const void *in_shift, const void *out_shift,
+                            void *grad, long long batch, int dtype)
+{
+    Lmme128Args args{left, right, grad, nullptr, Z, in_shift, out_shift};
+    if (mode == 1) return dtype == GOOM_C64 ? launch_ktile<float, 1>(ctx, args, batch) : launch_ktile<double, 1>(ctx, args, batch);
+    return dtype == GOOM_C64 ? launch_ktile<float, 2>(ctx, args, batch) : launch_ktile<double, 2>(ctx, args, batch);
 }
 
 } // namespace goom

@@ -14,6 +14,8 @@
 //            A~'^T [d, n];  B~'^T [m, d]  (found and taken out by the transposing kernels);  W~' [n, m]
 //   LMME     X~' = LMME(W~', B~'^T) [n, d];  Y~' = LMME(A~'^T, W~') [d, m]         (the forward kernels)
 //   finish   grad_A_ij = +- exp(Re A~'_ij + Re X~'_ij),  grad_B_jk = +- exp(Re B~'_jk + Re Y~'_jk)
+// For n = d = m = 128 the product kernel reads its operand transposed, takes the shift out and forms the gradient in its store
+// pass itself: only the shifts and W~' are prepared here.
 #include "goom_internal.h"
 
 namespace {
@@ -117,6 +119,49 @@ template <typename R, bool BY_ROW> __global__ __launch_bounds__(256) void transp
     }
 }
 
+// The shifts alone, for products that take them out of their operands themselves: r[b, i] = rint(max_j Re A[b, i, j]), one wave per
+// row; c[b, k] = rint(max_j Re B[b, j, k]), one thread per column (neighbouring threads read neighbouring columns).
+template <typename R> __global__ __launch_bounds__(256) void row_shift_kernel(const typename C2<R>::type *__restrict__ A, R *__restrict__ r, long long rows,
+                                                                              int cols)
+{
+    const int lane = threadIdx.x & 63;
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return; // whole wave
+    const typename C2<R>::type *src = A + (size_t)row * cols;
+    R top = neg_inf<R>();
+    for (int j = lane; j < cols; j += 64) {
+        const R v = src[j].x;
+        top = v > top ? v : top;
+    }
+    for (int s = 32; s > 0; s >>= 1) {
+        const R o = __shfl_xor(top, s, 64);
+        top = o > top ? o : top;
+    }
+    if (lane == 0) r[row] = whole_shift<R>(top);
+}
+
+template <typename R> __global__ __launch_bounds__(256) void col_shift_kernel(const typename C2<R>::type *__restrict__ B, R *__restrict__ c, int rows,
+                                                                              int cols)
+{
+    __shared__ R red[8][32];
+    const int per = (cols + 31) / 32; // workgroups per batch item: 32 columns each, 8 threads a column
+    const size_t b = blockIdx.x / per;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int k = (int)(blockIdx.x - b * per) * 32 + tx;
+    R top = neg_inf<R>();
+    if (k < cols)
+        for (int j = ty; j < rows; j += 8) {
+            const R v = B[(b * rows + j) * (size_t)cols + k].x;
+            top = v > top ? v : top;
+        }
+    red[ty][tx] = top;
+    __syncthreads();
+    if (ty == 0 && k < cols) {
+        for (int q = 1; q < 8; ++q) top = red[q][tx] > top ? red[q][tx] : top;
+        c[b * cols + k] = whole_shift<R>(top);
+    }
+}
+
 constexpr int kPerGroup = 1024; // elements of one batch item per workgroup of the elementwise kernels
 
 template <typename R> __device__ inline double log_for(double g)
@@ -194,6 +239,21 @@ template <typename R> int prepare_t(goom_ctx *ctx, const void *A, const void *B,
     return goom::check_hip(ctx, hipGetLastError(), "launch lmme_backward_prepare");
 }
 
+template <typename R> int prepare128_t(goom_ctx *ctx, const void *A, const void *B, const void *Cm, const void *G, void *r, void *c, void *W, long long batch)
+{
+    typedef typename C2<R>::type c2;
+    const int n = 128;
+    goom::prof_begin(ctx, "lmme_backward_prepare");
+    hipLaunchKernelGGL(row_shift_kernel<R>, dim3((unsigned)((batch * n + 3) / 4)), dim3(256), 0, ctx->stream, static_cast<const c2 *>(A), static_cast<R *>(r),
+                       batch * n, n);
+    hipLaunchKernelGGL(col_shift_kernel<R>, dim3((unsigned)(batch * ((n + 31) / 32))), dim3(256), 0, ctx->stream, static_cast<const c2 *>(B), static_cast<R *>(c), n,
+                       n);
+    hipLaunchKernelGGL(ratio_kernel<R>, dim3(groups_for(batch, n, n)), dim3(256), 0, ctx->stream, static_cast<const R *>(G), static_cast<const c2 *>(Cm),
+                       static_cast<const R *>(r), static_cast<const R *>(c), static_cast<c2 *>(W), n, n);
+    goom::prof_end(ctx);
+    return goom::check_hip(ctx, hipGetLastError(), "launch lmme_backward_prepare");
+}
+
 template <typename R> int finish_t(goom_ctx *ctx, const void *A, const void *B, const void *X, const void *Y, const void *r, const void *c, void *gA, void *gB,
                                    long long batch, int n, int d, int m)
 {
@@ -216,6 +276,12 @@ int launch_lmme_backward_prepare(goom_ctx *ctx, const void *A, const void *B, co
 {
     return dtype == GOOM_C64 ? prepare_t<float>(ctx, A, B, Cm, G, r, c, W, At, Bt, batch, n, d, m)
                              : prepare_t<double>(ctx, A, B, Cm, G, r, c, W, At, Bt, batch, n, d, m);
+}
+
+int launch_lmme_backward_prepare128(goom_ctx *ctx, const void *A, const void *B, const void *Cm, const void *G, void *r, void *c, void *W, long long batch,
+                                    int dtype)
+{
+    return dtype == GOOM_C64 ? prepare128_t<float>(ctx, A, B, Cm, G, r, c, W, batch) : prepare128_t<double>(ctx, A, B, Cm, G, r, c, W, batch);
 }
 
 int launch_lmme_backward_finish(goom_ctx *ctx, const void *A, const void *B, const void *X, const void *Y, const void *r, const void *c, void *gA, void *gB,
