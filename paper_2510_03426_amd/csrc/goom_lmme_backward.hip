@@ -119,25 +119,27 @@ template <typename R, bool BY_ROW> __global__ __launch_bounds__(256) void transp
     }
 }
 
-// The shifts alone, for products that take them out of their operands themselves: r[b, i] = rint(max_j Re A[b, i, j]), one wave per
+// The shifts alone, for products that take them out of their operands themselves: r[b, i] = rint(max_j Re A[b, i, j]), sixteen lanes a
 // row; c[b, k] = rint(max_j Re B[b, j, k]), one thread per column (neighbouring threads read neighbouring columns).
 template <typename R> __global__ __launch_bounds__(256) void row_shift_kernel(const typename C2<R>::type *__restrict__ A, R *__restrict__ r, long long rows,
                                                                               int cols)
 {
-    const int lane = threadIdx.x & 63;
-    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= rows) return; // whole wave
-    const typename C2<R>::type *src = A + (size_t)row * cols;
+    // sixteen lanes a row, four rows a wave
+    const int lane = threadIdx.x & 63, sub = lane & 15;
+    const long long row = ((long long)blockIdx.x * 4 + (threadIdx.x >> 6)) * 4 + (lane >> 4);
     R top = neg_inf<R>();
-    for (int j = lane; j < cols; j += 64) {
-        const R v = src[j].x;
-        top = v > top ? v : top;
+    if (row < rows) {
+        const typename C2<R>::type *src = A + (size_t)row * cols;
+        for (int j = sub; j < cols; j += 16) {
+            const R v = src[j].x;
+            top = v > top ? v : top;
+        }
     }
-    for (int s = 32; s > 0; s >>= 1) {
+    for (int s = 8; s > 0; s >>= 1) {
         const R o = __shfl_xor(top, s, 64);
         top = o > top ? o : top;
     }
-    if (lane == 0) r[row] = whole_shift<R>(top);
+    if (sub == 0 && row < rows) r[row] = whole_shift<R>(top);
 }
 
 template <typename R> __global__ __launch_bounds__(256) void col_shift_kernel(const typename C2<R>::type *__restrict__ B, R *__restrict__ c, int rows,
@@ -244,7 +246,7 @@ template <typename R> int prepare128_t(goom_ctx *ctx, const void *A, const void 
     typedef typename C2<R>::type c2;
     const int n = 128;
     goom::prof_begin(ctx, "lmme_backward_prepare");
-    hipLaunchKernelGGL(row_shift_kernel<R>, dim3((unsigned)((batch * n + 3) / 4)), dim3(256), 0, ctx->stream, static_cast<const c2 *>(A), static_cast<R *>(r),
+    hipLaunchKernelGGL(row_shift_kernel<R>, dim3((unsigned)((batch * n + 15) / 16)), dim3(256), 0, ctx->stream, static_cast<const c2 *>(A), static_cast<R *>(r),
                        batch * n, n);
     hipLaunchKernelGGL(col_shift_kernel<R>, dim3((unsigned)(batch * ((n + 31) / 32))), dim3(256), 0, ctx->stream, static_cast<const c2 *>(B), static_cast<R *>(c), n,
                        n);
