@@ -1137,7 +1137,8 @@ def test_signed_log_add(G, oracle, ctype):
 # dominant eigenvalue by delta moves a state at step t by t * delta, the same way for every term of the sum.)
 @pytest.mark.parametrize("T,d,batch,chunk,ctype,gain,cap", [
     (3000, 32, 3, 0, np.complex64, 1.02, 0.3), (2000, 32, 2, 0, np.complex64, 0.9, 0.05), (500, 16, 2, 7, np.complex64, 1.02, 0.07),
-    (100, 8, 2, 9, np.complex64, 1.02, 0.02), (400, 32, 1, 50, np.complex128, 1.02, 0.002), (64, 32, 2, 0, np.complex64, 1.02, 0.02)])
+    (100, 8, 2, 9, np.complex64, 1.02, 0.02), (400, 32, 1, 50, np.complex128, 1.02, 0.002), (64, 32, 2, 0, np.complex64, 1.02, 0.02),
+    (4100, 32, 1, 1024, np.complex64, 0.9, 0.05), (700, 16, 2, 64, np.complex64, 0.9, 0.05)])  # (chunk powers A^L in two stages: L = 32 * 32, 16 * 4)
 def test_affine_scan_time_invariant(G, oracle, T, d, batch, chunk, ctype, gain, cap):
     # one matrix per sequence, applied at every step (the paper's state-space layer): against the oracle
     # fed the matrix repeated T times
