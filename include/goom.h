@@ -392,7 +392,8 @@ int goom_scaled_exp_backward(goom_ctx *ctx, const void *scaled, const void *grad
  * A: [batch, n, d], B: [batch, d, m], C: [batch, n, m] GOOMs as given to and returned by goom_lmme; grad_C:
  * [batch, n, m], grad_A: [batch, n, d], grad_B: [batch, d, m] reals of the component type (device, caller-owned;
  * grad_A and grad_B overwritten).  Sizes and flags as for goom_lmme (flags go to both products).  workspace:
- * goom_lmme_backward_workspace_bytes(...) bytes, required: about (n m + 2 n d + 2 d m) GOOMs per batch item.
+ * goom_lmme_backward_workspace_bytes(...) bytes, required: about (n m + 2 n d + 2 d m) GOOMs per batch item
+ * (n m for n = d = m = 128 without GOOM_LMME_EXACT, where the product kernel transposes and exponentiates itself).
  * Errors: GOOM_EINVAL (null or misaligned pointers, sizes), GOOM_EUNSUPPORTED (sizes beyond goom_lmme's),
  * GOOM_EWORKSPACE. */
 int goom_lmme_backward(goom_ctx *ctx, const void *A, const void *B, const void *C, const void *grad_C, void *grad_A,

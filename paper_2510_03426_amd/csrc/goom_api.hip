@@ -1264,6 +1264,11 @@ LmmeBackwardPlan plan_lmme_backward(int64_t batch, int n, int d, int m, int dtyp
     p.r_bytes = align_up(bt * n * rb, 256);
     p.c_bytes = align_up(bt * m * rb, 256);
     p.w_bytes = align_up(bt * n * m * cb, 256);
+    if (n == 128 && d == 128 && m == 128 && !(flags & GOOM_LMME_EXACT)) {
+        // the full-size product kernel reads A and B themselves and writes the gradients: only the shifts and W~' pass through memory
+        p.at_bytes = p.x_bytes = p.bt_bytes = p.y_bytes = p.lmme_bytes = 0;
+        return p;
+    }
     p.at_bytes = p.x_bytes = align_up(bt * n * d * cb, 256);
     p.bt_bytes = p.y_bytes = align_up(bt * d * m * cb, 256);
     const size_t wa = goom_lmme_workspace_bytes(batch, n, m, d, dtype, flags), wb = goom_lmme_workspace_bytes(batch, d, n, m, dtype, flags);
