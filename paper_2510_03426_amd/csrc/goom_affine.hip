@@ -43,7 +43,7 @@ constexpr int kWalkWaves = 4; // chunks per workgroup
 template <int DP, bool TI, bool ADJ = false, bool IOS = false> __global__ __launch_bounds__(kWalkWaves * 64) void affine_walk_kernel(ChainArgs a, long long nchains)
 {
     typedef Comp<float> C;
-    constexpr int EPL = DP >= 32 ? 8 : 4; // entries of a row per lane
+    constexpr int EPL = DP / 4;           // entries of a row per lane (d = 64: one matrix for all steps only, it stays in registers)
     constexpr int LPR = DP / EPL;         // lanes that share a row
     constexpr int RPP = 64 / LPR;         // rows per pass
     constexpr int Q = DP / RPP;           // passes
@@ -726,7 +726,7 @@ bool affine_chunk_applies(const ChainArgs &args, int dp)
 {
     return (dp == 16 || dp == 32 || dp == 64) && args.n == dp && args.d == dp && args.m == dp + 1 && args.bias_mode == 1 &&
            args.bias_col == dp && args.init_mode == 0 && args.out_goom == nullptr && args.out_fact_steps == nullptr &&
-           args.out_fact_final != nullptr && args.fact_cols == dp + 16;
+           args.out_fact_final != nullptr && args.fact_cols == dp + 16 && args.io_shift == nullptr; // (a rescaled bias: the general kernel)
 }
 
 int dispatch_affine_chunk(goom_ctx *ctx, const ChainArgs &args, int dp, long long grid, const char *label)
@@ -742,8 +742,8 @@ int dispatch_affine_chunk(goom_ctx *ctx, const ChainArgs &args, int dp, long lon
 // zero), every state stored as GOOMs and / or the last one as a column of the chunk's factored total
 bool affine_walk_applies(const ChainArgs &args, int dp)
 {
-    return (dp == 16 || dp == 32) && args.n == dp && args.d == dp && args.m == 1 && args.bias_mode == 1 &&
-           (args.init_mode == 1 || args.init_mode == 3) &&
+    return (dp == 16 || dp == 32 || (dp == 64 && args.left_step_stride == 0 && !args.left_shift)) && args.n == dp && args.d == dp && args.m == 1 &&
+           args.bias_mode == 1 && (args.init_mode == 1 || args.init_mode == 3) &&
            (args.out_goom != nullptr || args.out_fact_final != nullptr || args.out_scaled != nullptr) &&
            !args.out_goom_last_only && args.out_fact_steps == nullptr &&
            ((args.out_goom == nullptr && args.out_scaled == nullptr) || args.bias_col == 0);
@@ -756,9 +756,11 @@ int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long
         return dp == 16 ? launch_walk<16, false, true>(ctx, args, nchains, label) : launch_walk<32, false, true>(ctx, args, nchains, label);
     }
     if (args.io_shift) { // bias and states rescaled step by step: over one matrix, GOOM or factored outputs
-        if (!ti || args.out_scaled) return goom::fail(ctx, GOOM_EUNSUPPORTED, "rescaled bias and states: the matrix-vector walk over one matrix only");
+        if (!ti || args.out_scaled) return goom::fail(ctx, GOOM_EUNSUPPORTED, "rescaled bias and states in the matrix-vector walk: one matrix for all steps only");
+        if (dp == 64) return launch_walk<64, true, false, true>(ctx, args, nchains, label);
         return dp == 16 ? launch_walk<16, true, false, true>(ctx, args, nchains, label) : launch_walk<32, true, false, true>(ctx, args, nchains, label);
     }
+    if (dp == 64) return launch_walk<64, true>(ctx, args, nchains, label); // (applies only with one matrix for all steps)
     if (dp == 16) return ti ? launch_walk<16, true>(ctx, args, nchains, label) : launch_walk<16, false>(ctx, args, nchains, label);
     return ti ? launch_walk<32, true>(ctx, args, nchains, label) : launch_walk<32, false>(ctx, args, nchains, label);
 }

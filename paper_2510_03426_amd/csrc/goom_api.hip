@@ -932,12 +932,11 @@ size_t goom_affine_scan_scaled_workspace_bytes(int64_t T, int d, int64_t batch, 
 // double chunk products only).
 static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H, void *scaled, void *logscale,
                       int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts, void *ws, size_t ws_bytes,
-                      const float *adjoint_shift = nullptr, bool adjoint_one_matrix = false, const float *io_shift = nullptr)
+                      const float *adjoint_shift = nullptr, const float *io_shift = nullptr)
 {
     // io_shift: [batch, T] whole numbers c_s; the bias enters as bias[s] e^(-c_s), the states leave as h_s e^(c_s) (the adjoint
-    // recurrence over one matrix: float GOOMs, d = 16 or 32, several chunks)
+    // recurrence over one matrix)
     // adjoint_shift: the adjoint recurrence, read from the forward pass's matrices (transposed, in reverse order, shifted);
-    // adjoint_one_matrix: those are one matrix per batch item, A: [batch, d, d] (not the time-invariant path: the shifts differ by step)
     goom_scan_opts plain = opts ? *opts : goom_scan_opts{0, 0};
     const bool ti = (plain.flags & GOOM_AFFINE_TIME_INVARIANT) != 0;
     plain.flags &= ~GOOM_AFFINE_TIME_INVARIANT;
@@ -961,7 +960,7 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
         return launch_scaled_exp(ctx, H, scaled, logscale, (size_t)batch * (size_t)T, d, dtype);
     }
     const int f64 = ap.f64 ? 1 : 0;
-    if ((adjoint_shift || adjoint_one_matrix) && (!adjoint_shift || !f64 || ti || want_scaled)) return fail(ctx, GOOM_EUNSUPPORTED, "transposed factors in reverse order: float GOOMs, d = 16 or 32, several chunks");
+    if (adjoint_shift && (!f64 || ti || want_scaled)) return fail(ctx, GOOM_EUNSUPPORTED, "transposed factors in reverse order: float GOOMs, d = 16 or 32, several chunks");
 
     ChainLaunch base;
     std::memset(&base, 0, sizeof base);
@@ -970,15 +969,14 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
     base.d = d;
     base.batch = batch;
     base.left = A;
-    base.left_batch_stride = (ti || adjoint_one_matrix) ? (long long)d * d * cb : (long long)T * d * d * cb;
-    base.left_step_stride = (ti || adjoint_one_matrix) ? 0 : (long long)d * d * cb; // a time-invariant matrix is every step's factor
+    base.left_batch_stride = ti ? (long long)d * d * cb : (long long)T * d * d * cb;
+    base.left_step_stride = ti ? 0 : (long long)d * d * cb; // a time-invariant matrix is every step's factor
     base.steps = T;
     base.bias_mode = 1;
     base.bias = bias;
     base.left_shift = adjoint_shift;
     base.io_shift = io_shift;
-    if (io_shift && !(ti && dtype == GOOM_C64 && (d == 16 || d == 32) && p.C > 1 && !want_scaled))
-        return fail(ctx, GOOM_EUNSUPPORTED, "rescaled bias and states: one matrix for all steps, float GOOMs, d = 16 or 32, several chunks");
+    if (io_shift && !(ti && !want_scaled)) return fail(ctx, GOOM_EUNSUPPORTED, "rescaled bias and states: one matrix for all steps, GOOM states");
 
     if (p.C == 1) {
         ChainLaunch l = base;
@@ -997,7 +995,7 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
     unsigned char *carries = totals + p.tot_bytes;
     unsigned char *gtot = carries + p.car_bytes;
     unsigned char *gcar = gtot + p.gtot_bytes;
-    if (ti && dtype == GOOM_C64 && (d == 16 || d == 32)) {
+    if (ti && dtype == GOOM_C64 && (d == 16 || d == 32 || d == 64)) {
         // phase 1, time-invariant: every chunk's total is [A^L | b*_c].  A^L once per batch item (a chain
         // of L equal factors), copied to all chunks; b*_c by a matrix-vector walk of the chunk from zero.
         ChainLaunch l = base;
@@ -1139,7 +1137,7 @@ int goom_affine_scan_scaled(goom_ctx *ctx, const void *A, const void *bias, cons
 struct AffineBackwardPlan {
     bool direct; // the adjoint scan reads the forward pass's matrices itself (transposed, in reverse order)
     bool one_matrix; // GOOM_AFFINE_TIME_INVARIANT: A is [batch, d, d] and so is its gradient
-    bool same_factor; // one_matrix, and the adjoint scan runs over A^T itself, its bias and states rescaled step by step
+    bool same_factor; // (= one_matrix) the adjoint scan runs over A^T itself, its bias and states rescaled step by step
     int nsplit;      // one_matrix: spans of steps whose outer products are summed by one workgroup each
     size_t at_bytes, vec_bytes, scan_bytes, uv_bytes, partial_bytes;
     size_t total() const { return at_bytes + 2 * vec_bytes + scan_bytes + uv_bytes + partial_bytes; }
@@ -1154,19 +1152,15 @@ static AffineBackwardPlan plan_affine_backward(long long T, int d, long long bat
     p.one_matrix = (plain.flags & GOOM_AFFINE_TIME_INVARIANT) != 0;
     plain.flags &= ~GOOM_AFFINE_TIME_INVARIANT;
     p.direct = plan_affine(T, d, batch, dtype, &plain).f64;
-    p.same_factor = false;
-    if (p.one_matrix && dtype == GOOM_C64 && (d == 16 || d == 32)) {
+    p.same_factor = p.one_matrix;
+    if (p.same_factor) {
         goom_scan_opts inv = plain;
         inv.flags |= GOOM_AFFINE_TIME_INVARIANT;
-        if (plan_affine(T, d, batch, dtype, &inv).p.C > 1) {
-            p.same_factor = true;
-            p.direct = false;
-            p.at_bytes = align_up((size_t)batch * d * d * cb, 256) + align_up((size_t)batch * (size_t)T * sizeof(float), 256);
-            p.vec_bytes = align_up((size_t)batch * (size_t)T * d * cb, 256);
-            p.scan_bytes = align_up(goom_affine_scan_workspace_bytes(T, d, batch, dtype, &inv), 256);
-        }
-    }
-    if (!p.same_factor) {
+        p.direct = false;
+        p.at_bytes = align_up((size_t)batch * d * d * cb, 256) + align_up((size_t)batch * (size_t)T * sizeof(float), 256);
+        p.vec_bytes = align_up((size_t)batch * (size_t)T * d * cb, 256);
+        p.scan_bytes = align_up(goom_affine_scan_workspace_bytes(T, d, batch, dtype, &inv), 256);
+    } else {
         // the transposed, reversed and rescaled copy of A, or only the shifts of its log-magnitudes, one per step
         p.at_bytes = p.direct ? align_up((size_t)batch * (size_t)T * sizeof(float), 256) : align_up((size_t)batch * (size_t)T * d * d * cb, 256);
         p.vec_bytes = align_up((size_t)batch * (size_t)T * d * cb, 256);
@@ -1215,15 +1209,14 @@ int goom_affine_scan_backward(goom_ctx *ctx, const void *A, const void *bias, co
     void *mu = w + p.at_bytes + p.vec_bytes;
     void *scan_ws = w + p.at_bytes + 2 * p.vec_bytes;
     if (p.same_factor) {
-        // one matrix, float GOOMs, d = 16 or 32: the adjoints lam_t themselves by the time-invariant scan over A^T, with G_t / h_t
-        // and lam_t passing through float GOOMs on the scale e^(c_t) (the scan rescales them beside its double exponents)
+        // one matrix: the adjoints lam_t themselves by the time-invariant scan over A^T, with G_t / h_t and lam_t passing through
+        // the GOOM arrays on the scale e^(c_t) (the scan rescales them beside its double exponents)
         float *cshift = reinterpret_cast<float *>(w + align_up((size_t)batch * d * d * 2 * comp_bytes(dtype), 256));
         if (int s = launch_affine_backward_prepare_one_matrix(ctx, A, H, grad_H, At, cshift, gt, T, d, batch, dtype)) return s;
         goom_scan_opts inv = plain;
         inv.flags |= GOOM_AFFINE_TIME_INVARIANT;
         ctx->prof_keep = true;
-        const int st = run_affine(ctx, At, gt, nullptr, mu, nullptr, nullptr, T, d, batch, dtype, &inv, p.scan_bytes ? scan_ws : nullptr, p.scan_bytes, nullptr, false,
-                                  cshift);
+        const int st = run_affine(ctx, At, gt, nullptr, mu, nullptr, nullptr, T, d, batch, dtype, &inv, p.scan_bytes ? scan_ws : nullptr, p.scan_bytes, nullptr, cshift);
         ctx->prof_keep = false;
         if (st) return st;
         unsigned char *U = w + p.at_bytes + 2 * p.vec_bytes + p.scan_bytes;
@@ -1231,22 +1224,16 @@ int goom_affine_scan_backward(goom_ctx *ctx, const void *A, const void *bias, co
                                                            batch, dtype);
     }
     // operands of the adjoint recurrence (transposed matrices in reverse time, G / h as GOOMs) ...
-    if (int s = launch_affine_backward_prepare(ctx, A, H, grad_H, p.direct ? nullptr : At, p.direct ? static_cast<float *>(At) : nullptr, gt, T, d, batch, dtype,
-                                               p.one_matrix))
+    if (int s = launch_affine_backward_prepare(ctx, A, H, grad_H, p.direct ? nullptr : At, p.direct ? static_cast<float *>(At) : nullptr, gt, T, d, batch, dtype))
         return s;
-    // ... the adjoints, by the forward scan itself (time-varying also over one matrix: the shifts differ by step) ...
+    // ... the adjoints, by the forward scan itself ...
     ctx->prof_keep = true;
     const int st = p.direct ? run_affine(ctx, A, gt, nullptr, mu, nullptr, nullptr, T, d, batch, dtype, &plain, p.scan_bytes ? scan_ws : nullptr, p.scan_bytes,
-                                         static_cast<const float *>(At), p.one_matrix)
+                                         static_cast<const float *>(At))
                             : run_affine(ctx, At, gt, nullptr, mu, nullptr, nullptr, T, d, batch, dtype, &plain, p.scan_bytes ? scan_ws : nullptr, p.scan_bytes);
     ctx->prof_keep = false;
     if (st) return st;
     // ... and the gradients
-    if (p.one_matrix) {
-        unsigned char *U = w + p.at_bytes + 2 * p.vec_bytes + p.scan_bytes;
-        return launch_affine_backward_gradients_one_matrix(ctx, A, bias, h0, H, mu, grad_A, grad_bias, grad_h0, U, U + p.uv_bytes, p.nsplit, T, d,
-                                                           batch, dtype);
-    }
     return launch_affine_backward_gradients(ctx, A, bias, h0, H, mu, grad_A, grad_bias, grad_h0, T, d, batch, dtype);
 }
 

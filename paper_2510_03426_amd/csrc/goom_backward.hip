@@ -108,7 +108,7 @@ template <typename R, int NW> __global__ __launch_bounds__(NW * 64) void bwd_pre
                                                                                             const typename C2<R>::type *__restrict__ H,
                                                                                             const R *__restrict__ G, typename C2<R>::type *__restrict__ At,
                                                                                             typename C2<R>::type *__restrict__ gt, long long T, int d,
-                                                                                            long long nsteps, int direct, int one_matrix)
+                                                                                            long long nsteps, int direct)
 {
     typedef typename C2<R>::type c2;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -127,7 +127,7 @@ template <typename R, int NW> __global__ __launch_bounds__(NW * 64) void bwd_pre
         for (int e = lane; e < nn; e += 64) dst[e] = c2{ninf, (R)0};
     } else {
         const R delta = ct - state_scale<R>(H + (size_t)(b * T + t + 1) * d, d); // c_t - c_{t+1}, a whole number
-        const c2 *src = A + (one_matrix ? (size_t)b : (size_t)(b * T + (T - s))) * d * d; // (one_matrix: the same factor at every step)
+        const c2 *src = A + (size_t)(b * T + (T - s)) * d * d;
         if (direct) { // a matrix too large for LDS (complex128 above 96 x 96): strided reads
             for (int e = lane; e < nn; e += 64) {
                 c2 v = src[(e % d) * d + e / d];
@@ -497,7 +497,7 @@ int launch_from_goom_backward(goom_ctx *ctx, const void *y, const void *gx, void
 }
 
 template <typename R, int NW> static int bwd_prepare_launch(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d,
-                                                           long long batch, bool one_matrix)
+                                                           long long batch)
 {
     typedef typename C2<R>::type c2;
     const size_t tile_bytes = (size_t)d * (d + 1) * sizeof(c2);
@@ -510,19 +510,18 @@ template <typename R, int NW> static int bwd_prepare_launch(goom_ctx *ctx, const
     const long long nsteps = batch * T;
     prof_begin(ctx, "affine_backward_prepare_operands");
     hipLaunchKernelGGL(kern, dim3((unsigned)((nsteps + NW - 1) / NW)), dim3(NW * 64), lds, ctx->stream, static_cast<const c2 *>(A), static_cast<const c2 *>(H),
-                       static_cast<const R *>(G), static_cast<c2 *>(At), static_cast<c2 *>(gt), T, d, nsteps, direct, one_matrix ? 1 : 0);
+                       static_cast<const R *>(G), static_cast<c2 *>(At), static_cast<c2 *>(gt), T, d, nsteps, direct);
     prof_end(ctx);
     return check_hip(ctx, hipGetLastError(), "launch bwd_prepare_kernel");
 }
 
 // waves (steps) per workgroup: as many as the matrices' LDS tiles allow
-template <typename R> static int bwd_prepare_t(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d, long long batch,
-                                               bool one_matrix)
+template <typename R> static int bwd_prepare_t(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, void *gt, long long T, int d, long long batch)
 {
     const size_t tile = (size_t)d * (d + 1) * 2 * sizeof(R);
-    if (4 * tile <= 64 * 1024) return bwd_prepare_launch<R, 4>(ctx, A, H, G, At, gt, T, d, batch, one_matrix);
-    if (2 * tile <= 96 * 1024) return bwd_prepare_launch<R, 2>(ctx, A, H, G, At, gt, T, d, batch, one_matrix);
-    return bwd_prepare_launch<R, 1>(ctx, A, H, G, At, gt, T, d, batch, one_matrix);
+    if (4 * tile <= 64 * 1024) return bwd_prepare_launch<R, 4>(ctx, A, H, G, At, gt, T, d, batch);
+    if (2 * tile <= 96 * 1024) return bwd_prepare_launch<R, 2>(ctx, A, H, G, At, gt, T, d, batch);
+    return bwd_prepare_launch<R, 1>(ctx, A, H, G, At, gt, T, d, batch);
 }
 
 // At[b] = A[b]^T, d x d (one matrix per batch item)
@@ -549,11 +548,11 @@ template <typename R> static int bwd_shift_t(goom_ctx *ctx, const void *H, const
 
 // At: the transposed, reversed, rescaled copy of A; or NULL, and then shift receives the shifts alone
 int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, float *shift, void *gt, long long T, int d,
-                                   long long batch, int dtype, bool one_matrix)
+                                   long long batch, int dtype)
 {
     if (batch * T > 0x7fffffffLL) return fail(ctx, GOOM_EUNSUPPORTED, "too many steps for one launch");
     if (!At) return dtype == GOOM_C64 ? bwd_shift_t<float>(ctx, H, G, shift, gt, T, d, batch) : bwd_shift_t<double>(ctx, H, G, shift, gt, T, d, batch);
-    return dtype == GOOM_C64 ? bwd_prepare_t<float>(ctx, A, H, G, At, gt, T, d, batch, one_matrix) : bwd_prepare_t<double>(ctx, A, H, G, At, gt, T, d, batch, one_matrix);
+    return dtype == GOOM_C64 ? bwd_prepare_t<float>(ctx, A, H, G, At, gt, T, d, batch) : bwd_prepare_t<double>(ctx, A, H, G, At, gt, T, d, batch);
 }
 
 // One matrix for all steps, scan over the matrix itself: At [batch, d, d] = A^T, shift[b, s] = c_t, gt as above

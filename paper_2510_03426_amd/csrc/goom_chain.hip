@@ -77,9 +77,8 @@ int launch_chain(goom_ctx *ctx, const ChainLaunch &l)
     a.acc_f64 = l.acc_f64;
     a.left_shift = l.left_shift;
     a.io_shift = l.io_shift;
-    if (l.io_shift && !(l.dtype == GOOM_C64 && !l.left_fact && !l.left_real && !l.io_c64 && l.m == 1 && l.bias_mode == 1 && l.left_step_stride == 0 &&
-                        !l.left_shift && !l.out_scaled && (l.d == 16 || l.d == 32) && l.n == l.d))
-        return fail(ctx, GOOM_EUNSUPPORTED, "rescaled bias and states: the matrix-vector walk over one matrix only");
+    if (l.io_shift && !(!l.left_fact && !l.left_real && !l.io_c64 && l.bias_mode == 1 && !l.left_shift && !l.out_scaled && !l.acc_f64))
+        return fail(ctx, GOOM_EUNSUPPORTED, "rescaled bias and states: GOOM factors with GOOM bias vectors only");
     if (l.left_shift && !(l.dtype == GOOM_C64 && !l.left_fact && !l.left_real && !l.io_c64 && (l.acc_f64 || (l.m == 1 && l.fact_f64)) && l.left_step_stride >= 0))
         return fail(ctx, GOOM_EUNSUPPORTED, "transposed factors in reverse order: double chunk products and the walk beside them only");
     if ((l.fact_f64 || l.acc_f64) && (l.dtype != GOOM_C64 || l.left_fact))

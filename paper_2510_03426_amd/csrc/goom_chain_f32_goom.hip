@@ -6,7 +6,6 @@ int dispatch_f32_goom(goom_ctx *ctx, const ChainArgs &args, int dp, int nw, long
 {
     if (args.acc_f64) return dispatch_affine_chunk_f64(ctx, args, dp, grid, label);
     if (args.fact_f64 && !affine_walk_applies(args, dp)) return goom::fail(ctx, GOOM_EUNSUPPORTED, "double carries are read by the matrix-vector walk only");
-    if (args.io_shift && !affine_walk_applies(args, dp)) return goom::fail(ctx, GOOM_EUNSUPPORTED, "rescaled bias and states: the matrix-vector walk only");
     if (small_applies(args, dp)) return dispatch_small(ctx, args, grid, label);
     if (fast_applies(args, dp, nw)) return dispatch_fast(ctx, args, dp, grid, label);
     if (ragged_applies(args, dp, nw)) return dispatch_ragged(ctx, args, dp, grid, label);

@@ -65,7 +65,8 @@ struct ChainArgs {
     // NULL, or [batch, steps] floats; the factor of step s is then the transpose of matrix steps - s of the array
     // `left` (any matrix for s = 0) with left_shift[s] added to every log-magnitude (-inf: a zero matrix)
     const float *left_shift;
-    // the matrix-vector walk over one matrix for all steps only: NULL, or [batch, steps] floats (whole numbers); the bias of step s
+    // the matrix-vector walk over one matrix for all steps and the general kernel with GOOM bias vectors: NULL, or [batch, steps] floats
+    // (whole numbers); the bias of step s
     // is then bias[s] e^(-io_shift[s]) and the state written for step s is h_s e^(+io_shift[s]): values far from 1 pass
     // through GOOM arrays of float components with log-magnitudes of ordinary size
     const float *io_shift;
@@ -631,6 +632,8 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
         // bias column (linear recurrence with bias): b_i, given as a GOOM or as a column
         // of the factored left factor, is added to entry (i, bias_col) in the log2 domain.
         const bool bias_lane = !FAST && a.bias_mode != 0 && slab_active && col == a.bias_col;
+        // bias and stored states rescaled by e^(-+io_shift[s]) (see ChainArgs): the shift joins the column's exponent, in double
+        const double ios = (!FAST && a.io_shift) ? (double)a.io_shift[item * a.steps + t0 + t] * kLog2e : 0.0;
         auto bias_term = [&](int i, double &blog, bool &bneg) { // blog = log2|b_i| - ecol
             blog = kNegBig;
             bneg = false;
@@ -638,7 +641,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
             if (a.bias_mode == 1) {
                 const IO *bp = reinterpret_cast<const IO *>(a.bias) + ((size_t)(item * a.steps + t0 + t) * n_rows + i) * 2;
                 R br = bp[0];
-                if (br > kNegInf) blog = (double)br * kLog2e - ecol;
+                if (br > kNegInf) blog = (double)br * kLog2e - ecol - ios; // (ios: the step's io_shift in powers of two, else 0)
                 bneg = Comp<R>::is_negative(bp[1]);
             } else {
                 const unsigned char *src = left0 + t * a.left_step_stride;
@@ -738,7 +741,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                     const int i = 16 * mt + Comp<R>::row_of(g, v);
                     const R x = acc[mt][v];
                     if (want_out && i < n_rows) {
-                        const R re = Comp<R>::out_re(x, nv[v], ecol);
+                        const R re = Comp<R>::out_re(x, nv[v], ecol + ios);
                         const IO im = x < (R)0 ? Comp<IO>::pi() : (IO)0;
                         IO *o = outp + (size_t)(i * mo + col) * 2;
                         if (sizeof(IO) == 4) {
@@ -766,7 +769,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd(sizeof(R), DP, NW)) void ch
                     const R xb = (col_nonzero && blog > kNegBig) ? exp2_of<R>(blog - (double)cm) : (R)0;
                     const R xs = xa + (bneg ? -xb : xb);
                     if (want_out && i < n_rows) {
-                        const R re = Comp<R>::out_re(xs, cms, ecol);
+                        const R re = Comp<R>::out_re(xs, cms, ecol + ios);
                         const IO im = xs < (R)0 ? Comp<IO>::pi() : (IO)0;
                         IO *o = outp + (size_t)(i * mo + col) * 2;
                         o[0] = (IO)re;

@@ -165,7 +165,7 @@ int launch_to_goom_backward(goom_ctx *ctx, const void *x, const void *g, void *g
 int launch_scaled_exp_backward(goom_ctx *ctx, const void *scaled, const void *g, void *gre, size_t n, int dtype);
 int launch_from_goom_backward(goom_ctx *ctx, const void *y, const void *gx, void *g, size_t n, int dtype, double eps);
 int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, const void *G, void *At, float *shift, void *gt, long long T, int d,
-                                   long long batch, int dtype, bool one_matrix = false); // one_matrix: A is [batch, d, d], every step's factor
+                                   long long batch, int dtype);
 int launch_affine_backward_gradients(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
                                      void *gb, void *gh0, long long T, int d, long long batch, int dtype);
 int launch_lmme128_backward(goom_ctx *ctx, int mode, const void *left, const void *right, const void *Z, const void *in_shift, const void *out_shift,
