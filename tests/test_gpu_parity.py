@@ -769,6 +769,7 @@ def test_scaled_exponentiation(G, oracle, ctype):
     (1000, 16, 2, 7, np.complex64, False, 1.05),
     (4000, 16, 2, 0, np.complex64, False, 1.3),    # magnitudes far outside float range
     (500, 32, 2, 25, np.complex64, True, 1.0),     # constant matrix
+    (400, 64, 2, 20, np.complex64, True, 1.0),     # constant 64 x 64 matrix: scaled states by the walk
     (64, 8, 2, 0, np.complex64, False, 1.05),      # through GOOM states in the workspace
     (257, 64, 1, 40, np.complex64, False, 1.05),
     (200, 16, 2, 16, np.complex128, False, 1.05),
