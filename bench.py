@@ -593,6 +593,19 @@ def recurrence(g, torch, dev, si):
     del gh
     g._ws = None
     torch.cuda.empty_cache()
+    # one 64 x 64 matrix per sequence: 64 sequences of 32,768 tokens
+    a64 = g.to_goom(torch.randn((64, 64, 64), device=dev, generator=si.device_generator(251003426 * 10 + 55, dev)) * (1.02 / 8.0))
+    b64 = g.to_goom(torch.randn((64, 32768, 64), device=dev, generator=si.device_generator(251003426 * 10 + 56, dev)))
+    h64 = g.affine_scan(a64, b64, time_invariant=True)
+    g64 = torch.randn((64, 32768, 64), device=dev, generator=si.device_generator(251003426 * 10 + 57, dev))
+    sec = timed(torch, lambda: g.affine_scan(a64, b64, out=h64, time_invariant=True))
+    secb = timed(torch, lambda: g.affine_scan_backward(a64, b64, h64, g64, time_invariant=True))
+    res["recurrence_time_invariant_d64_64seq_T32768"] = {
+        "ms": round(sec * 1e3, 3), "tokens_per_s": round(64 * 32768 / sec, 1), "backward_ms": round(secb * 1e3, 3),
+        "kernels_ms": kernel_times(g, lambda: g.affine_scan(a64, b64, out=h64, time_invariant=True))}
+    del a64, b64, h64, g64
+    g._ws = None
+    torch.cuda.empty_cache()
     # the elementwise ends of the recurrence as ops of their own, on the states just computed (nseq x T vectors of d):
     # signed log-add (24 B per element) and scaled exponentiation (12 B per element)
     o = torch.empty_like(h)

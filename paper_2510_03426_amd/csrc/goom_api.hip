@@ -1024,7 +1024,7 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
         }
         // A^L = (A^L1)^L2 shortens the chain of dependent products from L to L1 + L2 (one wave-sized chain per batch item: its
         // length is the whole cost).  The inner power goes to the second chunk's slot, which is overwritten afterwards.
-        const long long L1 = (f64 && p.L >= 64 && p.L % 16 == 0) ? (p.L >= 1024 && p.L % 32 == 0 ? 32 : 16) : 0;
+        const long long L1 = (p.L >= 64 && p.L % 16 == 0) ? (p.L >= 1024 && p.L % 32 == 0 ? 32 : 16) : 0;
         if (L1) {
             l.steps = L1;
             l.chunk_len = L1;
@@ -1035,10 +1035,10 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
             ChainLaunch o;
             std::memset(&o, 0, sizeof o);
             o.dp = p.dp;
-            o.dtype = GOOM_C128;
+            o.dtype = f64 ? GOOM_C128 : dtype;
             o.n = d;
             o.d = d;
-            o.m = d + 1;
+            o.m = f64 ? d + 1 : d; // (the double chunk kernel wrote a zero bias column, the float one none)
             o.batch = batch;
             o.left_fact = 1;
             o.left_fact_cols = p.tot.cols_padded;
@@ -1049,7 +1049,7 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
             o.chunk_len = o.steps;
             o.chunks_launched = 1;
             o.init_mode = 0;
-            o.bias_mode = 2; // (the factor's bias column is zero, and stays so)
+            o.bias_mode = f64 ? 2 : 0; // (the factor's bias column is zero, and stays so)
             o.bias_col = d;
             o.out_fact_final = totals;
             o.final_common_exponent = 1;
