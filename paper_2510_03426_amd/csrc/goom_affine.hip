@@ -742,7 +742,7 @@ int dispatch_affine_chunk(goom_ctx *ctx, const ChainArgs &args, int dp, long lon
 // zero), every state stored as GOOMs and / or the last one as a column of the chunk's factored total
 bool affine_walk_applies(const ChainArgs &args, int dp)
 {
-    return (dp == 16 || dp == 32 || (dp == 64 && args.left_step_stride == 0 && !args.left_shift)) && args.n == dp && args.d == dp && args.m == 1 &&
+    return (dp == 16 || dp == 32 || (dp == 64 && !args.left_shift)) && args.n == dp && args.d == dp && args.m == 1 &&
            args.bias_mode == 1 && (args.init_mode == 1 || args.init_mode == 3) &&
            (args.out_goom != nullptr || args.out_fact_final != nullptr || args.out_scaled != nullptr) &&
            !args.out_goom_last_only && args.out_fact_steps == nullptr &&
@@ -760,7 +760,7 @@ int dispatch_affine_walk(goom_ctx *ctx, const ChainArgs &args, int dp, long long
         if (dp == 64) return launch_walk<64, true, false, true>(ctx, args, nchains, label);
         return dp == 16 ? launch_walk<16, true, false, true>(ctx, args, nchains, label) : launch_walk<32, true, false, true>(ctx, args, nchains, label);
     }
-    if (dp == 64) return launch_walk<64, true>(ctx, args, nchains, label); // (applies only with one matrix for all steps)
+    if (dp == 64) return ti ? launch_walk<64, true>(ctx, args, nchains, label) : launch_walk<64, false>(ctx, args, nchains, label);
     if (dp == 16) return ti ? launch_walk<16, true>(ctx, args, nchains, label) : launch_walk<16, false>(ctx, args, nchains, label);
     return ti ? launch_walk<32, true>(ctx, args, nchains, label) : launch_walk<32, false>(ctx, args, nchains, label);
 }

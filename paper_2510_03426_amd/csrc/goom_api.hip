@@ -912,11 +912,8 @@ size_t goom_affine_scan_workspace_bytes(int64_t T, int d, int64_t batch, int dty
 
 // Scaled states (Section 4.3, eq. 27) come straight out of the matrix-vector walk where that kernel serves the
 // last phase; otherwise the states are written as GOOMs to the workspace and converted.
-// the scaled states are written by the matrix-vector walk itself (d = 64: with one matrix for all steps)
-static bool affine_scaled_is_fused(const ScanPlan &p, int d, int dtype, bool one_matrix)
-{
-    return dtype == GOOM_C64 && (d == 16 || d == 32 || (d == 64 && one_matrix)) && p.C > 1;
-}
+// the scaled states are written by the matrix-vector walk itself
+static bool affine_scaled_is_fused(const ScanPlan &p, int d, int dtype) { return dtype == GOOM_C64 && (d == 16 || d == 32 || d == 64) && p.C > 1; }
 
 static size_t affine_states_bytes(long long T, int d, long long batch, int dtype)
 {
@@ -928,8 +925,7 @@ size_t goom_affine_scan_scaled_workspace_bytes(int64_t T, int d, int64_t batch, 
     if (T <= 0 || d <= 0 || batch <= 0 || d > GOOM_MAX_DIM) return 0;
     if (dtype != GOOM_C64 && dtype != GOOM_C128) return 0;
     const AffinePlan ap = plan_affine(T, d, batch, dtype, opts);
-    const bool one_matrix = opts && (opts->flags & GOOM_AFFINE_TIME_INVARIANT);
-    return align_up(ap.total(), 256) + (affine_scaled_is_fused(ap.p, d, dtype, one_matrix) ? 0 : affine_states_bytes(T, d, batch, dtype));
+    return align_up(ap.total(), 256) + (affine_scaled_is_fused(ap.p, d, dtype) ? 0 : affine_states_bytes(T, d, batch, dtype));
 }
 
 // adjoint_shift: NULL, or [batch, T] floats: the recurrence then runs on the transposes of A's matrices in reverse
@@ -953,7 +949,7 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
     if (logscale && !aligned(logscale, comp_bytes(dtype))) return fail(ctx, GOOM_EINVAL, "misaligned data pointer");
     const AffinePlan ap = plan_affine(T, d, batch, dtype, opts);
     const ScanPlan &p = ap.p;
-    const bool fused = want_scaled && affine_scaled_is_fused(p, d, dtype, ti);
+    const bool fused = want_scaled && affine_scaled_is_fused(p, d, dtype);
     const size_t need = want_scaled ? align_up(ap.total(), 256) + (fused ? 0 : affine_states_bytes(T, d, batch, dtype)) : ap.total();
     if (int s = check_workspace(ctx, ws, ws_bytes, need)) return s;
     if (int s = need_ctx(ctx)) return s;
