@@ -706,6 +706,7 @@ size_t goom_lmme_workspace_bytes(int64_t batch, int n, int d, int m, int dtype, 
 {
     if (batch <= 0 || n <= 0 || d <= 0 || m <= 0 || (dtype != GOOM_C64 && dtype != GOOM_C128)) return 0;
     if (n == 128 && d == 128 && m == 128 && (flags & GOOM_LMME_EXACT)) return lmme128_shift_bytes(batch, dtype);
+    if (lmme_tall_applies(n, d, m, dtype)) return 0;
     if (!lmme_is_large(n, d, m)) return 0;
     if (n > GOOM_MAX_DIM_LMME || d > GOOM_MAX_DIM_LMME || m > GOOM_MAX_DIM_LMME) return 0;
     return dtype == GOOM_C64 ? lmme_large_workspace_bytes(batch, n, d, m) : lmme_large_f64_workspace_bytes(batch, n, d, m);
@@ -721,6 +722,13 @@ int goom_lmme(goom_ctx *ctx, const void *A, const void *B, void *C, int64_t batc
     if (n > GOOM_MAX_DIM_LMME || d > GOOM_MAX_DIM_LMME || m > GOOM_MAX_DIM_LMME)
         return fail(ctx, GOOM_EUNSUPPORTED, "n, d, m must be <= %d", GOOM_MAX_DIM_LMME);
     if (!aligned(A, 16) || !aligned(B, 16) || !aligned(C, 16)) return fail(ctx, GOOM_EINVAL, "complex data must be 16-byte aligned");
+    if (lmme_tall_applies(n, d, m, dtype)) {
+        // many rows against a small right operand (the input term of the state-space layer): rows streamed past B~ in registers
+        if (int s = need_ctx(ctx)) return s;
+        if (int s = launch_lmme_tall(ctx, A, B, C, batch, n, d, m)) return s;
+        if (flags & GOOM_LMME_EXACT) return launch_lmme_exact(ctx, A, B, C, batch, n, d, m, dtype);
+        return GOOM_OK;
+    }
     if (lmme_is_large(n, d, m)) {
         // beyond the register-resident kernels: scaled operands, a tiled GEMM and a store pass, through the workspace
         const bool f32 = dtype == GOOM_C64;

@@ -168,6 +168,9 @@ int launch_affine_backward_prepare(goom_ctx *ctx, const void *A, const void *H, 
                                    long long batch, int dtype);
 int launch_affine_backward_gradients(goom_ctx *ctx, const void *A, const void *bias, const void *h0, const void *H, const void *mu, void *gA,
                                      void *gb, void *gh0, long long T, int d, long long batch, int dtype);
+// goom_lmme_tall.hip: A [batch, n, d] of many rows against B [batch, d, m] with d, m <= 64 (float components)
+bool lmme_tall_applies(int n, int d, int m, int dtype);
+int launch_lmme_tall(goom_ctx *ctx, const void *A, const void *B, void *Cm, long long batch, int n, int d, int m);
 int launch_lmme128_backward(goom_ctx *ctx, int mode, const void *left, const void *right, const void *Z, const void *in_shift, const void *out_shift,
                             void *grad, long long batch, int dtype); // goom_lmme128.hip: a product of the backward pass with its operand transposed on the fly
 // backward of LMME (goom_lmme_backward.hip): shifts r [batch, n], c [batch, m]; W [batch, n, m], At [batch, d, n], Bt [batch, m, d] GOOMs

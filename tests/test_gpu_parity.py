@@ -193,6 +193,29 @@ def test_lmme_matches_oracle(G, oracle, shape):
     compare(got, re, sg, kap, name=f"lmme{shape}", max_ill_fraction=0.02)
 
 
+@pytest.mark.parametrize("shape,flags", [((3, 1024, 32, 32), 0), ((2, 200, 64, 64), 0), ((2, 130, 16, 8), 0), ((1, 1000, 24, 50), 0), ((5, 64, 4, 1), 0),
+                                         ((2, 77, 12, 33), 0), ((1, 300, 48, 20), 1), ((2, 128, 64, 64), 0), ((1, 17, 8, 8), 0), ((2, 257, 32, 17), 0)])
+def test_lmme_many_rows_small_right_operand(G, oracle, shape, flags):
+    # the shape of the state-space layer's input term (Section 4.3: B u_t for all steps at once): rows streamed past the right operand
+    b, n, d, m = shape
+    rng = np.random.default_rng(9)
+    say(f"tall lmme batch={b} n={n} d={d} m={m} flags={flags}")
+    A = oracle.to_goom(si.normal_f32(si.BASE_SEED + 26, 7, b * n * d).reshape(b, n, d))
+    B = oracle.to_goom(si.normal_f32(si.BASE_SEED + 27, 8, b * d * m).reshape(b, d, m))
+    A.real += rng.uniform(-1e4, 1e4, (b, n, 1)).astype(np.float32)  # row scales far outside float range
+    B.real += rng.uniform(-1e4, 1e4, (b, 1, m)).astype(np.float32)
+    A[0, 0, 0] = -np.inf       # a zero entry
+    A[b - 1, n - 1, :] = -np.inf  # an all-zero last row
+    if m > 2:
+        B[0, :, 1] = -np.inf   # an all-zero column
+    re, sg, kap = oracle.lmme(A, B, return_kappa=True)
+    got = host(G.lmme(dev(A), dev(B), flags=flags))
+    assert np.all(np.isneginf(got.real[b - 1, n - 1, :]))
+    if m > 2:
+        assert np.all(np.isneginf(got.real[0, :, 1]))
+    compare(got, re, sg, kap, name=f"tall lmme{shape}", max_ill_fraction=0.03)
+
+
 def test_lmme_far_outside_float_range(G, oracle):
     # log-magnitudes of order +-1e5: no float could hold the values, row/column shifts absorb them
     rng = np.random.default_rng(5)
