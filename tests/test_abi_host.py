@@ -103,8 +103,11 @@ def test_argument_validation_without_device(lib):
     assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 1, 0, None, 0) == EWS  # complex128 above 128: through the workspace too
     assert lib.goom_scan(None, p, None, p, 4, 200, 200, 1, 1, None, None, 0) == EWS  # and so do scans of such matrices
     assert lib.goom_scan_workspace_bytes(4, 200, 200, 1, 1, None) > lib.goom_scan_workspace_bytes(4, 200, 200, 1, 0, None) > 0
-    assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 0, 0, None, 0) == EWS
-    assert lib.goom_lmme_workspace_bytes(1, 200, 8, 8, 0, 0) > 0
+    assert lib.goom_lmme(None, p, p, p, 1, 200, 72, 8, 0, 0, None, 0) == EWS
+    assert lib.goom_lmme_workspace_bytes(1, 200, 72, 8, 0, 0) > 0
+    # many rows against a small right operand (float components, d and m up to 64): a kernel of its own, no workspace
+    assert lib.goom_lmme_workspace_bytes(1, 200, 8, 8, 0, 0) == 0
+    assert lib.goom_lmme(None, p, p, p, 1, 200, 8, 8, 0, 0, None, 0) == EINVAL and "context" in err(lib)
     assert lib.goom_lmme(None, p, p, p, 0, 8, 8, 8, 0, 0, None, 0) == EINVAL
     assert lib.goom_lmme(None, p, p, p, 1, 8, 8, 8, 0, 2, None, 0) == EINVAL
     # affine
