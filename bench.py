@@ -166,7 +166,10 @@ def main():
         torch.cuda.synchronize()
         rms = (time.perf_counter() - r0) / 3 * 1e3
         result["reduce"] = {"ms": round(rms, 4), "products_per_s": round(T / (rms * 1e-3), 1),
-                            "hbm_gbs": round(T * 8 * d * d / (rms * 1e-3) / 1e9, 1)}
+                            "hbm_gbs": round(T * 8 * d * d / (rms * 1e-3) / 1e9, 1),
+                            # every product of a reduction is needed: executed and useful flops coincide
+                            "lmme_tflops": round(2.0 * d ** 3 * T / (rms * 1e-3) / 1e12, 2),
+                            "pct_of_fp32_mfma_peak": round(2.0 * d ** 3 * T / (rms * 1e-3) / 157.3e12 * 100, 2)}
     if not args.no_extras and not args.basic_extras and d in (32, 64, 128):
         # the same scan fed with the real matrices themselves (4 bytes per entry in instead of 8; an extra of
         # the library, not the configuration `value` is quoted on)
@@ -229,18 +232,23 @@ def main():
         S = min(T, args.cpu_sample_steps)
         zs = z[:S].cpu().numpy()
         c0 = time.perf_counter()
-        re, sg = oracle.scan(zs)
+        re, sg, kap = oracle.scan(zs, return_kappa=True)
         cpu_s = time.perf_counter() - c0
         result["cpu_baseline"] = {
             "value": round(S / cpu_s, 2), "unit": "products/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"first {S} steps of the same chain (definitional log-sum-exp scan in double), {cpu_s:.1f} s",
         }
-        # the GPU result on the sampled prefix must agree with the oracle
+        # the GPU result on the sampled prefix must agree with the oracle: every entry whose sum the oracle finds well conditioned
+        # (cancellation factor of the last row-by-column sum at most 2^9, as in the parity tests) within 1e-4 relative or 1e-3
         got = g.scan(z[:S]).cpu().numpy()
-        well = np.isfinite(re)
-        err = np.abs(got.real.astype(np.float64) - re)[well]
-        tol = np.maximum(1e-3, 1e-4 * np.abs(re[well]))
-        result["cpu_baseline"]["gpu_entries_within_tolerance"] = round(float(np.mean(err <= tol)), 6)
+        finite = np.isfinite(re)
+        well = finite & (kap <= 2.0 ** 9)
+        err = np.abs(got.real.astype(np.float64) - re)
+        tol = np.maximum(1e-3, 1e-4 * np.abs(re))
+        result["cpu_baseline"]["ill_conditioned_fraction"] = round(float(1.0 - well.mean()), 6)
+        result["cpu_baseline"]["gpu_well_conditioned_entries_within_tolerance"] = round(float(np.mean(err[well] <= tol[well])), 9)
+        err, tol = err[finite], tol[finite]
+        result["cpu_baseline"]["gpu_entries_within_tolerance"] = round(float(np.mean(err <= tol)), 6)  # ill-conditioned ones included
 
     print(json.dumps(result), flush=True)
 

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgoom.so")
 SOURCES = ["goom_api.hip", "goom_codec.hip", "goom_chain.hip", "goom_reset.hip", "goom_lmme_exact.hip", "goom_chain_f32_goom.hip",
-           "goom_chain_f32_fact.hip", "goom_chain_f64_goom.hip", "goom_chain_f64_fact.hip", "goom_chain_f64_io32.hip", "goom_affine.hip", "goom_large.hip", "goom_large_f64.hip", "goom_lmme128.hip", "goom_chain256.hip", "goom_chain_small.hip", "goom_chain_ragged.hip", "goom_backward.hip", "goom_lmme_backward.hip", "goom_scan_backward.hip", "goom_lmme_tall.hip"]
+           "goom_chain_f32_fact.hip", "goom_chain_f64_goom.hip", "goom_chain_f64_fact.hip", "goom_chain_f64_io32.hip", "goom_affine.hip", "goom_large.hip", "goom_large_f64.hip", "goom_lmme128.hip", "goom_chain256.hip", "goom_chain_small.hip", "goom_chain_ragged.hip", "goom_backward.hip", "goom_lmme_backward.hip", "goom_scan_backward.hip", "goom_lmme_tall.hip", "goom_affine_seq.hip"]
 HEADERS = ["goom_internal.h", "goom_chain_kernel.h", "goom_chain_fast.h", "goom_codec_tables.h", "goom_large_scan.h", os.path.join("..", "..", "include", "goom.h")]
 
 FLAGS = [

@@ -911,6 +911,16 @@ static AffinePlan plan_affine(long long T, int d, long long batch, int dtype, co
     return ap;
 }
 
+// Batches of many sequences with a matrix per step (float components, d = 32, default chunking): each sequence is walked start
+// to end by one workgroup, which takes about 0.43 us a step whatever the batch (up to one workgroup per compute unit); the chunked
+// scan takes about 3.8 ns a token.
+constexpr long long kAffineSequentialMinBatch = 120;
+static bool affine_sequential_applies(long long T, int d, long long batch, int dtype, const goom_scan_opts *opts)
+{
+    const bool ti = opts && (opts->flags & GOOM_AFFINE_TIME_INVARIANT);
+    return dtype == GOOM_C64 && d == 32 && !ti && (!opts || opts->chunk_len == 0) && batch >= kAffineSequentialMinBatch && T >= 1;
+}
+
 size_t goom_affine_scan_workspace_bytes(int64_t T, int d, int64_t batch, int dtype, const goom_scan_opts *opts)
 {
     if (T <= 0 || d <= 0 || batch <= 0 || d > GOOM_MAX_DIM) return 0;
@@ -961,6 +971,9 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
     const size_t need = want_scaled ? align_up(ap.total(), 256) + (fused ? 0 : affine_states_bytes(T, d, batch, dtype)) : ap.total();
     if (int s = check_workspace(ctx, ws, ws_bytes, need)) return s;
     if (int s = need_ctx(ctx)) return s;
+    if (affine_sequential_applies(T, d, batch, dtype, opts) && !adjoint_shift && !io_shift)
+        // enough sequences to fill the chip one workgroup each: no chunks, every matrix read once
+        return goom_chain::launch_affine_seq(ctx, A, bias, h0, H, want_scaled ? scaled : nullptr, want_scaled ? logscale : nullptr, T, batch);
     const size_t cb = 2 * comp_bytes(dtype);
     if (want_scaled && !fused) {
         // the states as GOOMs behind the scan's own workspace, then their scaled exponentials

@@ -494,7 +494,9 @@ def test_scan_beyond_float_range(G, oracle):
 # ------------------------------------------------------------------------------ affine
 
 @pytest.mark.parametrize("T,d,batch,chunk", [(64, 8, 2, 0), (300, 32, 3, 32), (100, 16, 1, 9), (1, 32, 2, 0), (257, 64, 1, 40),
-                                             (1000, 32, 2, 5), (90, 128, 2, 16), (70, 100, 1, 0)])
+                                             (1000, 32, 2, 5), (90, 128, 2, 16), (70, 100, 1, 0),
+                                             # many sequences of d = 32: each walked start to end by one workgroup
+                                             (1, 32, 120, 0), (37, 32, 121, 0), (300, 32, 130, 0), (8, 32, 120, 0), (1000, 32, 120, 0)])
 def test_affine_scan_matches_oracle(G, oracle, T, d, batch, chunk):
     A, b = si.recurrence_inputs(si.BASE_SEED + 50, batch, T, d)
     Az, bz = oracle.to_goom(A), oracle.to_goom(b)
@@ -507,6 +509,46 @@ def test_affine_scan_matches_oracle(G, oracle, T, d, batch, chunk):
     re, sg, kap, well = with_sensitivity(fn, [Az, bz, h0], np.float32)
     got = host(G.affine_scan(dev(Az), dev(bz), dev(h0), chunk_len=chunk))
     compare(got, re, sg, kap, name=f"affine h0 T{T}d{d}", max_ill_fraction=0.05, well=well)
+
+
+def test_affine_scan_many_sequences_edge_cases(G, oracle):
+    # the walk of whole sequences (d = 32, 120 sequences or more) on states, rows, matrices and biases that are zero, on biases
+    # far above and far below the state, and on magnitudes far outside float range; a length that ends inside a round of steps
+    batch, T, d = 120, 45, 32
+    A, b = si.recurrence_inputs(si.BASE_SEED + 59, batch, T, d)
+    Az, bz = oracle.to_goom(A), oracle.to_goom(b)
+    zero = np.complex64(complex(-np.inf, 0.0))
+    bz[0, :5] = zero          # no bias for five steps and no initial state: the states are zero until step 5
+    Az[1, :, 3, :] = zero     # two rows of every matrix zero: those entries of the state are the bias alone
+    Az[1, :, 17, :] = zero
+    Az[2, 10] = zero          # a zero matrix: the state restarts from the bias
+    bz[3, 7] += 300           # a bias e^300 above the state, and one e^-300 below
+    bz[3, 20] -= 300
+    Az[4] += 40               # log-magnitudes reach 1800
+    bz[5] = zero              # nothing but zeros
+    Az[6, :, :, 5] = zero     # a zero column: one entry of the state never matters
+    bz[7, :, 8:] = zero       # only the first eight entries are driven
+    say("affine, many sequences: zeros and wide magnitudes")
+    fn = lambda a_, b_, h_: oracle.affine_scan(a_, b_, h0=h_, return_kappa=True)
+    re, sg, kap, well = with_sensitivity(fn, [Az, bz, None], np.float32)
+    got = host(G.affine_scan(dev(Az), dev(bz)))
+    assert np.all(np.isneginf(got[0, :5].real)) and np.all(np.isneginf(got[5].real)) and np.all(np.isneginf(re[5]))
+    assert re[4].max() > 1500
+    compare(got, re, sg, kap, name="affine, many sequences, edge cases", max_ill_fraction=0.05, well=well)
+    # the scaled states of the same sequences: zeros stay zeros, their log-scaling constant is -inf
+    sc, c = G.affine_scan_scaled(dev(Az), dev(bz), want_logscale=True)
+    sc, c = host(sc).astype(np.float64), host(c).astype(np.float64)
+    want, cw = oracle.scaled_exp(re + 1j * np.pi * sg)
+    assert np.all(sc[5] == 0) and np.all(np.isneginf(c[5])) and np.all(sc[0, :5] == 0) and np.all(np.isneginf(c[0, :5]))
+    top = np.argmax(np.where(np.isfinite(re), re, -np.inf), axis=-1)
+    top_well = np.take_along_axis(well, top[..., None], axis=-1)[..., 0] & np.isfinite(cw)
+    ok = well & top_well[..., None] & np.isfinite(re)
+    with np.errstate(invalid="ignore"):
+        bound = np.where(np.isfinite(re), tolerance(re, np.float32), 0.0) + np.where(np.isfinite(cw), tolerance(cw, np.float32), 0.0)[..., None]
+    ratio = (np.abs(sc - want) / (bound * np.abs(want) + 1e-30))[ok]
+    assert ok.mean() > 0.6 and ratio.max() <= 1, (ok.mean(), ratio.max())
+    with np.errstate(invalid="ignore"):
+        assert np.all(np.abs(c - cw)[top_well] <= tolerance(cw, np.float32)[top_well])
 
 
 # ---------------------------------------------------------------- selective resetting, Lyapunov
@@ -797,6 +839,8 @@ def test_scaled_exponentiation(G, oracle, ctype):
     (257, 64, 1, 40, np.complex64, False, 1.05),
     (200, 16, 2, 16, np.complex128, False, 1.05),
     (40, 32, 2, 0, np.complex64, False, 1.05),     # a single chunk
+    (121, 32, 122, 0, np.complex64, False, 1.05),   # many sequences: scaled states written by the sequential walk
+    (3000, 32, 120, 0, np.complex64, False, 1.3),   # the same, magnitudes far outside float range
 ])
 def test_affine_scan_scaled_states(G, oracle, T, d, batch, chunk, ctype, ti, gain):
     # the scaled exponentiation (Section 4.3, eq. 27) applied to the recurrence's states inside the scan: against the oracle's states, scaled by
