@@ -562,11 +562,22 @@ def recurrence(g, torch, dev, si):
     bz = g.to_goom(torch.randn((nseq, T, d), device=dev, generator=si.device_generator(251003426 * 10 + 52, dev)))
     h = torch.empty((nseq, T, d), dtype=torch.complex64, device=dev)
     sec = timed(torch, lambda: g.affine_scan(az, bz, out=h))
-    byts = (2 * az.numel() + 2 * bz.numel() + h.numel()) * 8  # the matrices and the inputs are read by two phases
+    kms = kernel_times(g, lambda: g.affine_scan(az, bz, out=h))
+    # with this many sequences each is walked start to end and the matrices and inputs are read once; the chunked scan reads them in
+    # two of its phases
+    reads = 1 if "affine_sequential_walk" in kms else 2
+    byts = (reads * az.numel() + reads * bz.numel() + h.numel()) * 8
     res["recurrence_128seq_T65536_d32"] = {
         "ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1),
         "hbm_gbs_algorithmic": round(byts / sec / 1e9, 1), "pct_of_hbm_peak": round(100 * byts / sec / 1e9 / HBM_PEAK_GBS, 2),
-        "kernels_ms": kernel_times(g, lambda: g.affine_scan(az, bz, out=h))}
+        "passes_over_the_matrices": reads, "kernels_ms": kms}
+    # the same recurrence cut into chunks (what a batch of fewer sequences gets): chunk products, carries, walk
+    L = 1024
+    sec = timed(torch, lambda: g.affine_scan(az, bz, out=h, chunk_len=L), 2)
+    byts2 = (2 * az.numel() + 2 * bz.numel() + h.numel()) * 8
+    res["recurrence_128seq_T65536_d32_chunked"] = {
+        "ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1), "chunk_len": L,
+        "hbm_gbs_algorithmic": round(byts2 / sec / 1e9, 1), "kernels_ms": kernel_times(g, lambda: g.affine_scan(az, bz, out=h, chunk_len=L))}
     # its backward pass: gradients with respect to the log-magnitudes of A and of the inputs, given those of the states
     gh = torch.randn((nseq, T, d), device=dev, generator=si.device_generator(251003426 * 10 + 53, dev))
     fn = lambda: g.affine_scan_backward(az, bz, h, gh)

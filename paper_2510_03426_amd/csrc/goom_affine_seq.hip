@@ -2,23 +2,24 @@
 // batches of many sequences: one workgroup walks one whole sequence, step after step, and reads every matrix once.
 //
 // With a hundred sequences or more there is no need to cut a sequence into chunks (whose products cost a matrix-matrix
-// product per step and a second pass over the matrices): a workgroup of eight waves keeps eight steps of its sequence's
-// matrices in flight, which is enough outstanding memory traffic per compute unit, and a step is a matrix-vector product
-// spread over the 512 lanes:
+// product per step and a second pass over the matrices): a workgroup keeps eight steps of its sequence's matrices in
+// flight, which is enough outstanding memory traffic per compute unit, and a step is a matrix-vector product.  The
+// work of a step falls into a part that does not depend on the running vector and a chain that does, and the eight
+// waves of the workgroup are split accordingly, one wave of each kind per SIMD, so that the first fills the waits of
+// the second:
 //
-//   * a lane loads two adjacent entries of a row (16 bytes; the workgroup's loads of a step cover the 8 KiB matrix
-//     contiguously), the sixteen lanes of a row agree on the row's power-of-two shift n_i and scale their entries to
-//     (+-) 2^(log2|A_ij| - n_i);
-//   * the vector lives in LDS as float mantissas with one whole-number exponent per group of four entries (the four rows
-//     a wave produces); a lane reads its two entries, brings them to the largest group exponent G and the row's sixteen
-//     lanes add up their products: entry i of A_t h is that sum times 2^(n_i + G);
-//   * the bias b_i joins on the new exponent of the wave's four rows (the largest of the four sums' and the four bias
-//     terms' exponents), the wave writes four mantissas and that exponent, and one workgroup barrier ends the step
-//     (mantissas and exponents alternate between two sets of LDS words, so one barrier a step is enough).
+//   * waves 0-3 scale the matrices, one step ahead: a lane loads four adjacent entries of a row (eight lanes a row,
+//     eight rows a wave), the row's lanes agree on its power-of-two shift n_i, and (+-) 2^(log2|A_ij| - n_i) goes to
+//     LDS with n_i.  They also write the states out, taking turns;
+//   * waves 4-7 run the chain: the vector lives in LDS as float mantissas with one whole-number exponent per group of
+//     eight entries (the rows one wave produces); a lane reads four scaled entries of its row and its four entries of
+//     the vector, brings these to the largest group exponent G, and the row's eight lanes add up their products: entry
+//     i of A_t h is that sum times 2^(n_i + G).  The bias b_i joins on the new exponent of the wave's eight rows (the
+//     largest of the eight sums' and the eight bias terms' exponents), the wave writes eight mantissas and that exponent.
 //
-// The state of step t - 1 leaves during step t, through one wave (the waves take turns): as a GOOM, and / or as the
-// scaled exponential of Section 4.3, eq. 27 with its log-scaling constant.  Nothing but A_t, b_t (read once) and the
-// outputs (written once) touches HBM.
+// One workgroup barrier ends a step: scaled matrices, mantissas and exponents alternate between two sets of LDS words.
+// The state of step t - 1 leaves during step t: as a GOOM, and / or as the scaled exponential of Section 4.3, eq. 27
+// with its log-scaling constant.  Nothing but A_t, b_t (read once) and the outputs (written once) touches HBM.
 #include "goom_chain_fast.h"
 #include <type_traits>
 
@@ -26,9 +27,10 @@ namespace goom_chain {
 
 namespace {
 
-constexpr int kSeqDepth = 8;          // steps of a sequence in flight, per lane one 16-byte piece of each
+constexpr int kSeqDepth = 8;          // steps of a sequence in flight
 constexpr int kSeqNone = -(1 << 28);  // exponent of a group of zeros
 constexpr int kSeqExpLimit = 1 << 27; // whole-number exponents are kept inside +- this
+constexpr int kSeqD = 32;
 
 struct SeqArgs {
     const unsigned char *A;    // [batch, T, 32, 32] complex64
@@ -40,6 +42,13 @@ struct SeqArgs {
     long long T;
 };
 
+struct SeqShared {
+    float sv[2][kSeqD * kSeqD]; // scaled, signed entries of a step's matrix
+    int n[2][kSeqD];            // its row shifts
+    float m[2][kSeqD];          // mantissas of the vector
+    int f[2][4];                // exponent of entries 8 w .. 8 w + 7 (the rows chain wave w produces)
+};
+
 // Workgroup barrier that orders LDS traffic only: the matrices in flight from HBM stay in flight across it (the
 // general barrier would wait for every outstanding load, and with it for the whole ring of prefetched steps).
 __device__ inline void lds_barrier()
@@ -49,88 +58,88 @@ __device__ inline void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// The ring of prefetched steps: loads the compiler does not track (it would make every step wait for the loads issued in it,
+// The rings of prefetched steps: loads the compiler does not track (it would make every step wait for the loads issued in it,
 // to copy what they fetched to the registers of the step that consumes it), issued and awaited by hand.  A load's registers
-// pass through wait_ring before their first use, so nothing reads them earlier; vector-memory loads return in the order of
-// issue, and stores issued in between only make the wait stricter.
+// pass through the wait before their first use, so nothing reads them earlier; a wave's vector-memory loads return in the
+// order of issue, and stores issued in between only make the wait stricter.
 typedef float f2 __attribute__((ext_vector_type(2)));
-__device__ inline void load_ring(f4 &m, f2 &b, const unsigned char *pm, const unsigned char *pb)
+__device__ inline void load_matrix_part(f4 &x, f4 &y, const unsigned char *p)
 {
-    asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx2 %1, %3, off" : "=&v"(m), "=&v"(b) : "v"(pm), "v"(pb) : "memory");
+    asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx4 %1, %2, off offset:16" : "=&v"(x), "=&v"(y) : "v"(p) : "memory");
 }
-// the pair issued kSeqDepth steps ago has landed once at most 2 (kSeqDepth - 1) newer loads are outstanding
-template <int NEWER> __device__ inline void wait_ring(f4 &m, f2 &b)
+__device__ inline void load_bias_entry(f2 &b, const unsigned char *p) { asm volatile("global_load_dwordx2 %0, %1, off" : "=&v"(b) : "v"(p) : "memory"); }
+// what was issued kSeqDepth steps ago has landed once at most NEWER younger loads are outstanding
+template <int NEWER> __device__ inline void wait_matrix_part(f4 &x, f4 &y) { asm volatile("s_waitcnt vmcnt(%2)" : "+v"(x), "+v"(y) : "n"(NEWER) : "memory"); }
+template <int NEWER> __device__ inline void wait_bias_entry(f2 &b) { asm volatile("s_waitcnt vmcnt(%1)" : "+v"(b) : "n"(NEWER) : "memory"); }
+
+constexpr float kSeqHi = 1.44269502162933349609375f; // float nearest log2(e)
+constexpr float kSeqLo = 1.925963033500011e-8f;      // log2(e) - kSeqHi
+
+// whole-number exponent at or above log2 of a magnitude given by its natural logarithm; kSeqNone for a zero
+__device__ inline int exponent_above(float re)
 {
-    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(m), "+v"(b) : "n"(NEWER) : "memory");
+    const float e = __builtin_amdgcn_fmed3f(__builtin_ceilf(re * kSeqHi), -(float)kSeqExpLimit, (float)kSeqExpLimit);
+    return re > -__builtin_huge_valf() ? (int)e : kSeqNone;
+}
+// (+-) 2^(re log2(e) - f) for a whole number f, the product with log2(e) carried in two floats
+__device__ inline float scaled_term(float re, float im, int f)
+{
+    float x = __builtin_fmaf(re, kSeqHi, -(float)f);
+    x = __builtin_fmaf(re, kSeqLo, x);
+    return Comp<float>::apply_sign(__builtin_amdgcn_exp2f(x), im);
 }
 
-__device__ inline int imax3(int a, int b, int c)
-{
-    const int m = a > b ? a : b;
-    return m > c ? m : c;
-}
-
-__global__ __launch_bounds__(512) void affine_seq_kernel(SeqArgs a)
+// ---- waves 0-3: the matrices, one step ahead of the chain, and the outputs
+__device__ __forceinline__ void seq_matrix_waves(const SeqArgs &a, SeqShared &s, int wave, int lane)
 {
     typedef Comp<float> C;
-    constexpr int D = 32;
-    __shared__ __align__(16) float mbuf[2][D];   // mantissas of the vector
-    __shared__ __align__(16) int fbuf[2][D / 4]; // exponent of entries 4 w .. 4 w + 3 (the rows wave w produces)
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int row = tid >> 4;         // sixteen lanes a row
-    const int cpos = tid & 15;        // the lane's columns: 2 cpos, 2 cpos + 1
-    const int src_group = cpos >> 1;  // the group those two entries of the vector belong to
-    const int ent = lane & 31;        // entry handled when this wave writes a state out
+    constexpr int D = kSeqD;
     const long long T = a.T;
     const size_t item = blockIdx.x;
-    const unsigned char *Ap = a.A + item * (size_t)T * (D * D * 8) + (size_t)tid * 16;
-    const unsigned char *bp = a.bias + item * (size_t)T * (D * 8) + (size_t)row * 8;
+    const int row = 8 * wave + (lane >> 3); // eight lanes a row
+    const int cq = lane & 7;                // the lane's columns: 4 cq .. 4 cq + 3
+    const int ent = lane & 31;              // entry handled when this wave writes a state out
+    const unsigned char *Ap = a.A + item * (size_t)T * (D * D * 8) + (size_t)(row * D + 4 * cq) * 8;
     unsigned char *og = a.out_goom ? a.out_goom + item * (size_t)T * (D * 8) + (size_t)ent * 8 : nullptr;
     float *os = a.out_scaled ? a.out_scaled + item * (size_t)T * D + ent : nullptr;
     float *ol = a.out_logscale ? a.out_logscale + item * (size_t)T : nullptr;
-    const float kHi = 1.44269502162933349609375f; // float nearest log2(e)
-    const float kLo = 1.925963033500011e-8f;      // log2(e) - kHi
     const float kNegInf = -__builtin_huge_valf();
 
-    // whole-number exponent at or above log2 of a magnitude given by its natural logarithm; kSeqNone for a zero
-    auto exponent_above = [&](float re) {
-        const float e = __builtin_amdgcn_fmed3f(__builtin_ceilf(re * kHi), -(float)kSeqExpLimit, (float)kSeqExpLimit);
-        return re > kNegInf ? (int)e : kSeqNone;
-    };
-    // (+-) 2^(re log2(e) - f) for a whole number f, the product with log2(e) carried in two floats
-    auto scaled_term = [&](float re, float im, int f) {
-        float x = __builtin_fmaf(re, kHi, -(float)f);
-        x = __builtin_fmaf(re, kLo, x);
-        return C::apply_sign(__builtin_amdgcn_exp2f(x), im);
-    };
-
-    // the starting vector goes to the set of LDS words that step 0 reads
-    if (wave == 0) {
-        float2 v = float2{kNegInf, 0.0f};
-        if (a.h0) v = *reinterpret_cast<const float2 *>(a.h0 + (item * D + ent) * 8);
-        int f = exponent_above(v.x);
-        f = C::imax(f, C::dpp<0xB1>(f));
-        f = C::imax(f, C::dpp<0x4E>(f)); // the four entries of a group sit in one quad of lanes
-        mbuf[1][ent] = v.x > kNegInf ? scaled_term(v.x, v.y, f) : 0.0f;
-        if ((lane & 3) == 0) fbuf[1][ent >> 2] = f;
-    }
-
-    f4 ring[kSeqDepth];
-    f2 bring[kSeqDepth];
+    f4 ra[kSeqDepth], rb[kSeqDepth]; // slot j mod kSeqDepth: the lane's four entries of matrix j
 #pragma unroll
     for (int u = 0; u < kSeqDepth; ++u) {
         const long long t = u < T ? u : T - 1;
-        load_ring(ring[u], bring[u], Ap + (size_t)t * (D * D * 8), bp + (size_t)t * (D * 8));
+        load_matrix_part(ra[u], rb[u], Ap + (size_t)t * (D * D * 8));
     }
-    __syncthreads();
+
+    // the lane's four entries scaled by the row's power of two and signed, to LDS set `set`
+    auto scale_rows = [&](const f4 &x, const f4 &y, int set) {
+        const float re[4] = {x[0], x[2], y[0], y[2]}, im[4] = {x[1], x[3], y[1], y[3]};
+        int key = C::key_of(vmax_raw(vmax_raw(re[0], re[1]), vmax_raw(re[2], re[3])) * kSeqHi);
+        key = C::imax(key, C::dpp<0xB1>(key));
+        key = C::imax(key, C::dpp<0x4E>(key));
+        key = C::imax(key, C::dpp<0x141>(key));
+        const float mx = C::of_key(key);
+        const bool zero_row = !(mx > -1.0e30f);
+        const float nf = zero_row ? 0.0f : __builtin_amdgcn_fmed3f(__builtin_ceilf(mx), -(float)kSeqExpLimit, (float)kSeqExpLimit);
+        const float nsub = zero_row ? __builtin_huge_valf() : nf;
+        f4 sv;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float xx = __builtin_fmaf(re[e], kSeqHi, -nsub);
+            xx = __builtin_fmaf(re[e], kSeqLo, xx);
+            const float v = __builtin_amdgcn_exp2f(xx); // 2^-inf = 0 covers zero entries and zero rows
+            const float kf = __builtin_fmaf(im[e], 0.318309886183790671538f, 12582912.0f);
+            sv[e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) | (__builtin_bit_cast(int, kf) << 31));
+        }
+        *reinterpret_cast<f4 *>(&s.sv[set][row * D + 4 * cq]) = sv;
+        if (cq == 0) s.n[set][row] = (int)nf;
+    };
 
     // the state held in LDS set `set` (that of step t) leaves through this wave's lanes
     auto write_state = [&](int set, long long t) {
-        const float m = mbuf[set][ent];
-        const int f = fbuf[set][ent >> 2];
+        const float m = s.m[set][ent];
+        const int f = s.f[set][ent >> 3];
         if (og) {
             float2 o;
             o.x = C::out_re_f(m, (float)f); // (-inf for a zero)
@@ -140,10 +149,8 @@ __global__ __launch_bounds__(512) void affine_seq_kernel(SeqArgs a)
         if (os || ol) {
             // scaled exponentiation (Section 4.3, eq. 27): with c the log of the largest magnitude, exp(z_i - c + 2) is the entry over the
             // largest entry, times e^2; the exponents only enter c
-            int g = f;
-            g = C::imax(g, C::dpp<0x141>(g));
-            g = C::imax(g, C::dpp<0x140>(g)); // over the four groups of a row of sixteen lanes
-            g = C::xor16_imax(g);             // all eight groups
+            const int4 fa = *reinterpret_cast<const int4 *>(&s.f[set][0]);
+            const int g = C::imax(C::imax(fa.x, fa.y), C::imax(fa.z, fa.w));
             const int down = f - g;
             const float v = __builtin_ldexpf(m, down > -300 ? down : -300);
             float am = __builtin_fabsf(v);
@@ -153,68 +160,135 @@ __global__ __launch_bounds__(512) void affine_seq_kernel(SeqArgs a)
         }
     };
 
-    // one step; u = t mod kSeqDepth picks the ring's registers and the LDS sets at compile time
+    // matrix 0, before the chain's first step
+    wait_matrix_part<2 * (kSeqDepth - 1)>(ra[0], rb[0]);
+    scale_rows(ra[0], rb[0], 0);
+    {
+        const long long tn = kSeqDepth < T ? kSeqDepth : T - 1;
+        load_matrix_part(ra[0], rb[0], Ap + (size_t)tn * (D * D * 8));
+    }
+    lds_barrier();
+
+    // while the chain takes step t: the state of step t - 1 out, matrix t + 1 scaled.  u = t mod kSeqDepth picks the ring's
+    // registers and the LDS sets at compile time
     auto step = [&](auto uc, auto prefetch, long long t) {
         constexpr int u = decltype(uc)::value;
         constexpr bool kPrefetch = decltype(prefetch)::value; // false after the last full round: the rest of the sequence has landed
-        constexpr int kOdd = 1; // (tb is a multiple of the depth, which is even: the sets alternate with u)
-        const int rs = (u + kOdd) & 1, ws = u & 1;
-        // ---- the vector of step t - 1
-        const float2 mm = *reinterpret_cast<const float2 *>(&mbuf[rs][2 * cpos]);
-        const int fsrc = fbuf[rs][src_group];
-        const int4 fa = *reinterpret_cast<const int4 *>(&fbuf[rs][0]);
-        const int4 fb = *reinterpret_cast<const int4 *>(&fbuf[rs][4]);
-        if (t > 0 && wave == u) write_state(rs, t - 1);
-        // ---- this step's matrix: the row's shift, the lane's two entries scaled and signed
-        if constexpr (kPrefetch) wait_ring<2 * (kSeqDepth - 1)>(ring[u], bring[u]);
-        const f4 raw = ring[u];
-        const f2 b = bring[u];
-        int key = C::key_of(vmax_raw(raw[0], raw[2]) * kHi);
-        key = C::imax(key, C::dpp<0xB1>(key));
-        key = C::imax(key, C::dpp<0x4E>(key));
-        key = C::imax(key, C::dpp<0x141>(key));
-        key = C::imax(key, C::dpp<0x140>(key));
-        const float mx = C::of_key(key);
-        const bool zero_row = !(mx > -1.0e30f);
-        const float nf = zero_row ? 0.0f : __builtin_amdgcn_fmed3f(__builtin_ceilf(mx), -(float)kSeqExpLimit, (float)kSeqExpLimit);
-        const float nsub = zero_row ? __builtin_huge_valf() : nf;
-        const int n = (int)nf;
-        float sv[2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            float x = __builtin_fmaf(raw[2 * e], kHi, -nsub);
-            x = __builtin_fmaf(raw[2 * e], kLo, x);
-            const float v = __builtin_amdgcn_exp2f(x); // 2^-inf = 0 covers zero entries and zero rows
-            const float kf = __builtin_fmaf(raw[2 * e + 1], 0.318309886183790671538f, 12582912.0f);
-            sv[e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) | (__builtin_bit_cast(int, kf) << 31));
+        constexpr int slot = (u + 1) % kSeqDepth;
+        if (t > 0 && wave == (u & 3)) write_state((u + 1) & 1, t - 1);
+        if constexpr (kPrefetch) wait_matrix_part<2 * (kSeqDepth - 1)>(ra[slot], rb[slot]);
+        scale_rows(ra[slot], rb[slot], (u + 1) & 1); // (past the end: the last matrix again, read by nobody)
+        if constexpr (kPrefetch) {
+            // the registers are free: matrix t + 1 + kSeqDepth (past the end the last one again: every step of a full round issues its loads)
+            const long long tn = t + 1 + kSeqDepth < T ? t + 1 + kSeqDepth : T - 1;
+            load_matrix_part(ra[slot], rb[slot], Ap + (size_t)tn * (D * D * 8));
         }
+        lds_barrier();
+    };
+    static_assert(kSeqDepth == 8, "the steps are written out");
+    long long tb = 0;
+    for (; tb + kSeqDepth <= T; tb += kSeqDepth) {
+        step(std::integral_constant<int, 0>{}, std::true_type{}, tb);
+        step(std::integral_constant<int, 1>{}, std::true_type{}, tb + 1);
+        step(std::integral_constant<int, 2>{}, std::true_type{}, tb + 2);
+        step(std::integral_constant<int, 3>{}, std::true_type{}, tb + 3);
+        step(std::integral_constant<int, 4>{}, std::true_type{}, tb + 4);
+        step(std::integral_constant<int, 5>{}, std::true_type{}, tb + 5);
+        step(std::integral_constant<int, 6>{}, std::true_type{}, tb + 6);
+        step(std::integral_constant<int, 7>{}, std::true_type{}, tb + 7);
+    }
+    // Everything still in flight lands before the last, partial round: from here on the compiler is free to reuse a ring register
+    // that no step reads any more, and a load still on its way would overwrite whatever it put there.
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(ra[0]), "+v"(ra[1]), "+v"(ra[2]), "+v"(ra[3]), "+v"(ra[4]), "+v"(ra[5]), "+v"(ra[6]), "+v"(ra[7]), "+v"(rb[0]), "+v"(rb[1]),
+                   "+v"(rb[2]), "+v"(rb[3]), "+v"(rb[4]), "+v"(rb[5]), "+v"(rb[6]), "+v"(rb[7])
+                 :
+                 : "memory");
+    const int rest = (int)(T - tb); // (the same for the whole workgroup)
+    if (rest > 0) step(std::integral_constant<int, 0>{}, std::false_type{}, tb);
+    if (rest > 1) step(std::integral_constant<int, 1>{}, std::false_type{}, tb + 1);
+    if (rest > 2) step(std::integral_constant<int, 2>{}, std::false_type{}, tb + 2);
+    if (rest > 3) step(std::integral_constant<int, 3>{}, std::false_type{}, tb + 3);
+    if (rest > 4) step(std::integral_constant<int, 4>{}, std::false_type{}, tb + 4);
+    if (rest > 5) step(std::integral_constant<int, 5>{}, std::false_type{}, tb + 5);
+    if (rest > 6) step(std::integral_constant<int, 6>{}, std::false_type{}, tb + 6);
+    if (wave == 0) write_state((int)((T - 1) & 1), T - 1);
+}
+
+// ---- waves 4-7: the chain
+__device__ __forceinline__ void seq_chain_waves(const SeqArgs &a, SeqShared &s, int kw, int lane)
+{
+    typedef Comp<float> C;
+    constexpr int D = kSeqD;
+    const long long T = a.T;
+    const size_t item = blockIdx.x;
+    const int row = 8 * kw + (lane >> 3);
+    const int cq = lane & 7;
+    const int src_group = cq >> 1; // the group the lane's four entries of the vector belong to
+    const unsigned char *bp = a.bias + item * (size_t)T * (D * 8) + (size_t)row * 8;
+    const float kNegInf = -__builtin_huge_valf();
+
+    f2 br[kSeqDepth]; // slot t mod kSeqDepth: the row's bias of step t
+#pragma unroll
+    for (int u = 0; u < kSeqDepth; ++u) {
+        const long long t = u < T ? u : T - 1;
+        load_bias_entry(br[u], bp + (size_t)t * (D * 8));
+    }
+    // the starting vector goes to the set of LDS words that step 0 reads
+    if (kw == 0) {
+        const int ent = lane & 31;
+        float2 v = float2{kNegInf, 0.0f};
+        if (a.h0) v = *reinterpret_cast<const float2 *>(a.h0 + (item * D + ent) * 8);
+        int f = exponent_above(v.x);
+        f = C::imax(f, C::dpp<0xB1>(f));
+        f = C::imax(f, C::dpp<0x4E>(f));
+        f = C::imax(f, C::dpp<0x141>(f)); // the eight entries of a group sit in eight adjacent lanes
+        s.m[1][ent] = v.x > kNegInf ? scaled_term(v.x, v.y, f) : 0.0f;
+        if ((lane & 7) == 0) s.f[1][ent >> 3] = f;
+    }
+    lds_barrier();
+
+    auto step = [&](auto uc, auto prefetch, long long t) {
+        constexpr int u = decltype(uc)::value;
+        constexpr bool kPrefetch = decltype(prefetch)::value;
+        constexpr int rs = (u + 1) & 1, ws = u & 1; // sets of the vector read and written (tb is a multiple of the depth, which is even)
+        constexpr int ms = u & 1;                   // set of the scaled matrix
+        const f4 sv = *reinterpret_cast<const f4 *>(&s.sv[ms][row * D + 4 * cq]);
+        const int n = s.n[ms][row];
+        const f4 hm = *reinterpret_cast<const f4 *>(&s.m[rs][4 * cq]);
+        const int fsrc = s.f[rs][src_group];
+        const int4 fa = *reinterpret_cast<const int4 *>(&s.f[rs][0]);
+        if constexpr (kPrefetch) wait_bias_entry<kSeqDepth - 1>(br[u]);
+        const f2 b = br[u];
         const int eb = exponent_above(b[0]);
-        // ---- row i of A_t h_{t-1}: the sixteen lanes' products on the exponent n_i + G
-        const int G = imax3(imax3(fa.x, fa.y, fa.z), imax3(fa.w, fb.x, fb.y), C::imax(fb.z, fb.w));
+        // ---- row i of A_t h_{t-1}: the eight lanes' products on the exponent n_i + G
+        const int G = C::imax(C::imax(fa.x, fa.y), C::imax(fa.z, fa.w));
         const int down = fsrc - G;
-        float part = __builtin_fmaf(sv[0], mm.x, sv[1] * mm.y);
+        float part = sv[0] * hm[0];
+        part = __builtin_fmaf(sv[1], hm[1], part);
+        part = __builtin_fmaf(sv[2], hm[2], part);
+        part = __builtin_fmaf(sv[3], hm[3], part);
         part = __builtin_ldexpf(part, down > -300 ? down : -300);
         part = add_dpp<0xB1>(part);
         part = add_dpp<0x4E>(part);
         part = add_dpp<0x141>(part);
-        part = add_dpp<0x140>(part);
-        // ---- new exponent of the wave's four entries: the largest among the four sums and the four bias terms
+        // ---- new exponent of the wave's eight entries: the largest among the eight sums and the eight bias terms
         int ep;
         (void)__builtin_frexpf(part, &ep);
-        const int erow = C::imax(part != 0.0f ? ep + n + G : kSeqNone, eb);
-        int F = C::xor16_imax(erow);
+        int F = C::imax(part != 0.0f ? ep + n + G : kSeqNone, eb);
+        F = C::imax(F, C::dpp<0x140>(F)); // the other row in these sixteen lanes
+        F = C::xor16_imax(F);
         F = C::xor32_imax(F);
         F = F > kSeqNone ? (F < 2 * kSeqExpLimit ? F : 2 * kSeqExpLimit) : kSeqNone; // (float log-magnitudes resolve nothing out there)
         const int up = n + G - F; // at most 0 for a non-zero sum
         float mant = __builtin_ldexpf(part, up > -300 ? (up < 300 ? up : 300) : -300);
         mant += scaled_term(b[0], b[1], F); // (a zero bias, log-magnitude -inf, adds 2^-inf = 0)
         const bool none = __builtin_amdgcn_ballot_w64(mant != 0.0f) == 0; // a group of zeros carries no exponent
-        if (cpos == 0) mbuf[ws][row] = mant;
-        if (lane == 0) fbuf[ws][wave] = none ? kSeqNone : F;
+        if (cq == 0) s.m[ws][row] = mant;
+        if (lane == 0) s.f[ws][kw] = none ? kSeqNone : F;
         if constexpr (kPrefetch) {
-            // the registers are free: step t + kSeqDepth (past the end the last step again: every step of a full round issues its pair)
             const long long tn = t + kSeqDepth < T ? t + kSeqDepth : T - 1;
-            load_ring(ring[u], bring[u], Ap + (size_t)tn * (D * D * 8), bp + (size_t)tn * (D * 8));
+            load_bias_entry(br[u], bp + (size_t)tn * (D * 8));
         }
         lds_barrier();
     };
@@ -229,15 +303,11 @@ __global__ __launch_bounds__(512) void affine_seq_kernel(SeqArgs a)
         step(std::integral_constant<int, 6>{}, std::true_type{}, tb + 6);
         step(std::integral_constant<int, 7>{}, std::true_type{}, tb + 7);
     }
-    static_assert(kSeqDepth == 8, "the steps are written out");
-    // Everything still in flight lands before the last, partial round: from here on the compiler is free to reuse a ring register
-    // that no step reads any more, and a load still on its way would overwrite whatever it put there.
     asm volatile("s_waitcnt vmcnt(0)"
-                 : "+v"(ring[0]), "+v"(ring[1]), "+v"(ring[2]), "+v"(ring[3]), "+v"(ring[4]), "+v"(ring[5]), "+v"(ring[6]), "+v"(ring[7]), "+v"(bring[0]),
-                   "+v"(bring[1]), "+v"(bring[2]), "+v"(bring[3]), "+v"(bring[4]), "+v"(bring[5]), "+v"(bring[6]), "+v"(bring[7])
+                 : "+v"(br[0]), "+v"(br[1]), "+v"(br[2]), "+v"(br[3]), "+v"(br[4]), "+v"(br[5]), "+v"(br[6]), "+v"(br[7])
                  :
-                 : "memory");
-    const int rest = (int)(T - tb); // (the same for the whole workgroup)
+                 : "memory"); // (as in the matrix waves: nothing in flight into registers the last, partial round may reuse)
+    const int rest = (int)(T - tb);
     if (rest > 0) step(std::integral_constant<int, 0>{}, std::false_type{}, tb);
     if (rest > 1) step(std::integral_constant<int, 1>{}, std::false_type{}, tb + 1);
     if (rest > 2) step(std::integral_constant<int, 2>{}, std::false_type{}, tb + 2);
@@ -245,7 +315,18 @@ __global__ __launch_bounds__(512) void affine_seq_kernel(SeqArgs a)
     if (rest > 4) step(std::integral_constant<int, 4>{}, std::false_type{}, tb + 4);
     if (rest > 5) step(std::integral_constant<int, 5>{}, std::false_type{}, tb + 5);
     if (rest > 6) step(std::integral_constant<int, 6>{}, std::false_type{}, tb + 6);
-    if (wave == 0) write_state((int)((T - 1) & 1), T - 1);
+}
+
+// Both kinds of waves pass the same barriers: one after their set-up, one at the end of every step.
+__global__ __launch_bounds__(512) void affine_seq_kernel(SeqArgs a)
+{
+    __shared__ __align__(16) SeqShared s;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (wave < 4)
+        seq_matrix_waves(a, s, wave, lane);
+    else
+        seq_chain_waves(a, s, wave - 4, lane);
 }
 
 } // namespace

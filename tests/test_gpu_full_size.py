@@ -331,7 +331,10 @@ def test_config5_recurrence_full_size(G, oracle):
         del x
     xin = next(si.device_normal_blocks(si.BASE_SEED * 10 + 52, nseq, (T, d), device, nseq))[1]
     bz = G.to_goom(xin).view(batch, heads, T, d)
+    # with this many sequences the library walks each of them start to end; a batch of fewer gets the chunked scan (chunk products,
+    # carries, walk), run here on the same input with the chunk length it would choose
     h = G.affine_scan(az, bz)
+    got_chunked = {p: host(G.affine_scan(azf[p:p + 1], bz.view(nseq, T, d)[p:p + 1])[0]) for p in picks}
     torch.cuda.synchronize()
     hf = h.view(nseq, T, d)
     fn = lambda a_, b_: oracle.affine_scan(a_, b_, return_kappa=True)
@@ -347,5 +350,6 @@ def test_config5_recurrence_full_size(G, oracle):
         # float walk alone, as in a sequential float evaluation: the stated tolerance holds on every entry
         # the oracle marks well conditioned
         compare(got, re, sg, kap, name=f"config 5 sequence {p}", max_ill_fraction=0.05, well=well)
+        compare(got_chunked[p], re, sg, kap, name=f"config 5 sequence {p}, chunked scan", max_ill_fraction=0.05, well=well)
         say(f"    |h_T| = exp({got.real[-1].max():.1f})")
     del az, bz, h

@@ -496,25 +496,28 @@ def test_scan_beyond_float_range(G, oracle):
 @pytest.mark.parametrize("T,d,batch,chunk", [(64, 8, 2, 0), (300, 32, 3, 32), (100, 16, 1, 9), (1, 32, 2, 0), (257, 64, 1, 40),
                                              (1000, 32, 2, 5), (90, 128, 2, 16), (70, 100, 1, 0),
                                              # many sequences of d = 32: each walked start to end by one workgroup
-                                             (1, 32, 120, 0), (37, 32, 121, 0), (300, 32, 130, 0), (8, 32, 120, 0), (1000, 32, 120, 0)])
+                                             (1, 32, 96, 0), (37, 32, 97, 0), (300, 32, 130, 0), (8, 32, 96, 0), (1000, 32, 100, 0)])
 def test_affine_scan_matches_oracle(G, oracle, T, d, batch, chunk):
     A, b = si.recurrence_inputs(si.BASE_SEED + 50, batch, T, d)
     Az, bz = oracle.to_goom(A), oracle.to_goom(b)
     say(f"affine T={T} d={d} batch={batch} chunk={chunk}")
     fn = lambda a_, b_, h_: oracle.affine_scan(a_, b_, h0=h_, return_kappa=True)
-    re, sg, kap, well = with_sensitivity(fn, [Az, bz, None], np.float32)
+    # (two random probes underestimate an entry's sensitivity tenfold about once in 10^4 entries: with a million entries and more,
+    # the oracle probes four times)
+    nprobe = 4 if batch * T * d > 500000 else 2
+    re, sg, kap, well = with_sensitivity(fn, [Az, bz, None], np.float32, nprobe=nprobe)
     got = host(G.affine_scan(dev(Az), dev(bz), chunk_len=chunk))
     compare(got, re, sg, kap, name=f"affine T{T}d{d}", max_ill_fraction=0.05, well=well)
     h0 = oracle.to_goom(si.normal_f32(si.BASE_SEED + 51, 9, batch * d).reshape(batch, d))
-    re, sg, kap, well = with_sensitivity(fn, [Az, bz, h0], np.float32)
+    re, sg, kap, well = with_sensitivity(fn, [Az, bz, h0], np.float32, nprobe=nprobe)
     got = host(G.affine_scan(dev(Az), dev(bz), dev(h0), chunk_len=chunk))
     compare(got, re, sg, kap, name=f"affine h0 T{T}d{d}", max_ill_fraction=0.05, well=well)
 
 
 def test_affine_scan_many_sequences_edge_cases(G, oracle):
-    # the walk of whole sequences (d = 32, 120 sequences or more) on states, rows, matrices and biases that are zero, on biases
+    # the walk of whole sequences (d = 32, 96 sequences or more) on states, rows, matrices and biases that are zero, on biases
     # far above and far below the state, and on magnitudes far outside float range; a length that ends inside a round of steps
-    batch, T, d = 120, 45, 32
+    batch, T, d = 96, 45, 32
     A, b = si.recurrence_inputs(si.BASE_SEED + 59, batch, T, d)
     Az, bz = oracle.to_goom(A), oracle.to_goom(b)
     zero = np.complex64(complex(-np.inf, 0.0))
