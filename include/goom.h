@@ -332,7 +332,11 @@ int goom_scaled_exp(goom_ctx *ctx, const void *z, void *scaled, void *logscale, 
 /* h[b, t] = A[b, t] h[b, t-1] + bias[b, t], h[b, -1] = h0[b] (NULL = zero vector), over
  * GOOMs.  A: [batch, T, d, d]; bias: [batch, T, d]; h0: NULL or [batch, d];
  * H: [batch, T, d].  Scanned as products of the augmented matrices [A | bias; 0 | 1]
- * whose last row is kept implicit.
+ * whose last row is kept implicit.  A batch of 96 sequences or more with a matrix per step,
+ * float components, d = 32 and opts->chunk_len == 0 is not scanned: every sequence is walked
+ * start to end by one workgroup, every matrix read once (the results are those of a sequential
+ * float evaluation; whole-number exponents are kept within +-2^28, i.e. log-magnitudes within
+ * +-1.8e8, beyond which a float log-magnitude resolves nothing anyway).
  * workspace: goom_affine_scan_workspace_bytes(...) bytes. */
 #define GOOM_AFFINE_TIME_INVARIANT 0x1u /* goom_scan_opts.flags: one matrix per batch item, A: [batch, d, d],
                                            applied at every step (the paper's state-space layer has constant
