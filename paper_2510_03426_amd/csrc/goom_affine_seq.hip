@@ -39,6 +39,7 @@ struct SeqArgs {
     unsigned char *out_goom;   // NULL or [batch, T, 32] complex64
     float *out_scaled;         // NULL or [batch, T, 32]
     float *out_logscale;       // NULL or [batch, T]
+    const float *left_shift;   // adjoint recurrence only: [batch, T] floats (see ChainArgs::left_shift)
     long long T;
 };
 
@@ -67,6 +68,19 @@ __device__ inline void load_matrix_part(f4 &x, f4 &y, const unsigned char *p)
 {
     asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx4 %1, %2, off offset:16" : "=&v"(x), "=&v"(y) : "v"(p) : "memory");
 }
+// the same four entries of a row of the transpose (source rows 256 bytes apart), and the step's shift
+__device__ inline void load_matrix_part_transposed(f2 &e0, f2 &e1, f2 &e2, f2 &e3, float &sh, const unsigned char *p, const float *ps)
+{
+    asm volatile("global_load_dwordx2 %0, %5, off\n\tglobal_load_dwordx2 %1, %5, off offset:256\n\tglobal_load_dwordx2 %2, %5, off offset:512\n\t"
+                 "global_load_dwordx2 %3, %5, off offset:768\n\tglobal_load_dword %4, %6, off"
+                 : "=&v"(e0), "=&v"(e1), "=&v"(e2), "=&v"(e3), "=&v"(sh)
+                 : "v"(p), "v"(ps)
+                 : "memory");
+}
+template <int NEWER> __device__ inline void wait_matrix_part_transposed(f2 &e0, f2 &e1, f2 &e2, f2 &e3, float &sh)
+{
+    asm volatile("s_waitcnt vmcnt(%5)" : "+v"(e0), "+v"(e1), "+v"(e2), "+v"(e3), "+v"(sh) : "n"(NEWER) : "memory");
+}
 __device__ inline void load_bias_entry(f2 &b, const unsigned char *p) { asm volatile("global_load_dwordx2 %0, %1, off" : "=&v"(b) : "v"(p) : "memory"); }
 // what was issued kSeqDepth steps ago has landed once at most NEWER younger loads are outstanding
 template <int NEWER> __device__ inline void wait_matrix_part(f4 &x, f4 &y) { asm volatile("s_waitcnt vmcnt(%2)" : "+v"(x), "+v"(y) : "n"(NEWER) : "memory"); }
@@ -90,7 +104,9 @@ __device__ inline float scaled_term(float re, float im, int f)
 }
 
 // ---- waves 0-3: the matrices, one step ahead of the chain, and the outputs
-__device__ __forceinline__ void seq_matrix_waves(const SeqArgs &a, SeqShared &s, int wave, int lane)
+// ADJ: the adjoint recurrence's factors, read from the forward pass's matrices: step s takes the transpose of matrix T - s (any
+// matrix for s = 0) and adds left_shift[s] to its log-magnitudes (-inf: a zero matrix).
+template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqArgs &a, SeqShared &s, int wave, int lane)
 {
     typedef Comp<float> C;
     constexpr int D = kSeqD;
@@ -99,22 +115,60 @@ __device__ __forceinline__ void seq_matrix_waves(const SeqArgs &a, SeqShared &s,
     const int row = 8 * wave + (lane >> 3); // eight lanes a row
     const int cq = lane & 7;                // the lane's columns: 4 cq .. 4 cq + 3
     const int ent = lane & 31;              // entry handled when this wave writes a state out
-    const unsigned char *Ap = a.A + item * (size_t)T * (D * D * 8) + (size_t)(row * D + 4 * cq) * 8;
+    const unsigned char *Ap = a.A + item * (size_t)T * (D * D * 8) + (ADJ ? (size_t)(4 * cq * D + row) * 8 : (size_t)(row * D + 4 * cq) * 8);
+    [[maybe_unused]] const float *shp = ADJ ? a.left_shift + item * (size_t)T : nullptr;
     unsigned char *og = a.out_goom ? a.out_goom + item * (size_t)T * (D * 8) + (size_t)ent * 8 : nullptr;
     float *os = a.out_scaled ? a.out_scaled + item * (size_t)T * D + ent : nullptr;
     float *ol = a.out_logscale ? a.out_logscale + item * (size_t)T : nullptr;
     const float kNegInf = -__builtin_huge_valf();
 
-    f4 ra[kSeqDepth], rb[kSeqDepth]; // slot j mod kSeqDepth: the lane's four entries of matrix j
-#pragma unroll
-    for (int u = 0; u < kSeqDepth; ++u) {
-        const long long t = u < T ? u : T - 1;
-        load_matrix_part(ra[u], rb[u], Ap + (size_t)t * (D * D * 8));
-    }
+    // slot j mod kSeqDepth: the lane's four entries of the factor of step j (and, transposed, its shift)
+    [[maybe_unused]] f4 ra[kSeqDepth], rb[kSeqDepth];
+    [[maybe_unused]] f2 q0[kSeqDepth], q1[kSeqDepth], q2[kSeqDepth], q3[kSeqDepth];
+    [[maybe_unused]] float qs[kSeqDepth];
+    constexpr int kNewer = (ADJ ? 5 : 2) * (kSeqDepth - 1); // loads issued after a slot's own until its turn comes again
+    auto load_slot = [&](auto sc, long long j) { // factor of step j (past the end: the last one again)
+        constexpr int k = decltype(sc)::value;
+        const long long jj = j < T ? j : T - 1;
+        if constexpr (ADJ) {
+            const long long src = jj > 0 ? T - jj : T - 1;
+            load_matrix_part_transposed(q0[k], q1[k], q2[k], q3[k], qs[k], Ap + (size_t)src * (D * D * 8), shp + jj);
+        } else {
+            load_matrix_part(ra[k], rb[k], Ap + (size_t)jj * (D * D * 8));
+        }
+    };
+    auto wait_slot = [&](auto sc) {
+        constexpr int k = decltype(sc)::value;
+        if constexpr (ADJ)
+            wait_matrix_part_transposed<kNewer>(q0[k], q1[k], q2[k], q3[k], qs[k]);
+        else
+            wait_matrix_part<kNewer>(ra[k], rb[k]);
+    };
+    load_slot(std::integral_constant<int, 0>{}, 0);
+    load_slot(std::integral_constant<int, 1>{}, 1);
+    load_slot(std::integral_constant<int, 2>{}, 2);
+    load_slot(std::integral_constant<int, 3>{}, 3);
+    load_slot(std::integral_constant<int, 4>{}, 4);
+    load_slot(std::integral_constant<int, 5>{}, 5);
+    load_slot(std::integral_constant<int, 6>{}, 6);
+    load_slot(std::integral_constant<int, 7>{}, 7);
 
     // the lane's four entries scaled by the row's power of two and signed, to LDS set `set`
-    auto scale_rows = [&](const f4 &x, const f4 &y, int set) {
-        const float re[4] = {x[0], x[2], y[0], y[2]}, im[4] = {x[1], x[3], y[1], y[3]};
+    auto scale_rows = [&](auto sc, int set) {
+        constexpr int k = decltype(sc)::value;
+        float re[4], im[4];
+        if constexpr (ADJ) {
+            const f2 q[4] = {q0[k], q1[k], q2[k], q3[k]};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                re[e] = q[e][0] + qs[k];
+                im[e] = q[e][1];
+            }
+        } else {
+            const f4 x = ra[k], y = rb[k];
+            re[0] = x[0], re[1] = x[2], re[2] = y[0], re[3] = y[2];
+            im[0] = x[1], im[1] = x[3], im[2] = y[1], im[3] = y[3];
+        }
         int key = C::key_of(vmax_raw(vmax_raw(re[0], re[1]), vmax_raw(re[2], re[3])) * kSeqHi);
         key = C::imax(key, C::dpp<0xB1>(key));
         key = C::imax(key, C::dpp<0x4E>(key));
@@ -160,13 +214,10 @@ __device__ __forceinline__ void seq_matrix_waves(const SeqArgs &a, SeqShared &s,
         }
     };
 
-    // matrix 0, before the chain's first step
-    wait_matrix_part<2 * (kSeqDepth - 1)>(ra[0], rb[0]);
-    scale_rows(ra[0], rb[0], 0);
-    {
-        const long long tn = kSeqDepth < T ? kSeqDepth : T - 1;
-        load_matrix_part(ra[0], rb[0], Ap + (size_t)tn * (D * D * 8));
-    }
+    // the factor of step 0, before the chain's first step
+    wait_slot(std::integral_constant<int, 0>{});
+    scale_rows(std::integral_constant<int, 0>{}, 0);
+    load_slot(std::integral_constant<int, 0>{}, kSeqDepth);
     lds_barrier();
 
     // while the chain takes step t: the state of step t - 1 out, matrix t + 1 scaled.  u = t mod kSeqDepth picks the ring's
@@ -176,13 +227,10 @@ __device__ __forceinline__ void seq_matrix_waves(const SeqArgs &a, SeqShared &s,
         constexpr bool kPrefetch = decltype(prefetch)::value; // false after the last full round: the rest of the sequence has landed
         constexpr int slot = (u + 1) % kSeqDepth;
         if (t > 0 && wave == (u & 3)) write_state((u + 1) & 1, t - 1);
-        if constexpr (kPrefetch) wait_matrix_part<2 * (kSeqDepth - 1)>(ra[slot], rb[slot]);
-        scale_rows(ra[slot], rb[slot], (u + 1) & 1); // (past the end: the last matrix again, read by nobody)
-        if constexpr (kPrefetch) {
-            // the registers are free: matrix t + 1 + kSeqDepth (past the end the last one again: every step of a full round issues its loads)
-            const long long tn = t + 1 + kSeqDepth < T ? t + 1 + kSeqDepth : T - 1;
-            load_matrix_part(ra[slot], rb[slot], Ap + (size_t)tn * (D * D * 8));
-        }
+        if constexpr (kPrefetch) wait_slot(std::integral_constant<int, slot>{});
+        scale_rows(std::integral_constant<int, slot>{}, (u + 1) & 1); // (past the end: the last factor again, read by nobody)
+        // the registers are free: the factor of step t + 1 + kSeqDepth (every step of a full round issues its loads)
+        if constexpr (kPrefetch) load_slot(std::integral_constant<int, slot>{}, t + 1 + kSeqDepth);
         lds_barrier();
     };
     static_assert(kSeqDepth == 8, "the steps are written out");
@@ -199,11 +247,24 @@ __device__ __forceinline__ void seq_matrix_waves(const SeqArgs &a, SeqShared &s,
     }
     // Everything still in flight lands before the last, partial round: from here on the compiler is free to reuse a ring register
     // that no step reads any more, and a load still on its way would overwrite whatever it put there.
-    asm volatile("s_waitcnt vmcnt(0)"
-                 : "+v"(ra[0]), "+v"(ra[1]), "+v"(ra[2]), "+v"(ra[3]), "+v"(ra[4]), "+v"(ra[5]), "+v"(ra[6]), "+v"(ra[7]), "+v"(rb[0]), "+v"(rb[1]),
-                   "+v"(rb[2]), "+v"(rb[3]), "+v"(rb[4]), "+v"(rb[5]), "+v"(rb[6]), "+v"(rb[7])
-                 :
-                 : "memory");
+    if constexpr (ADJ) {
+        asm volatile("s_waitcnt vmcnt(0)"
+                     : "+v"(q0[0]), "+v"(q0[1]), "+v"(q0[2]), "+v"(q0[3]), "+v"(q0[4]), "+v"(q0[5]), "+v"(q0[6]), "+v"(q0[7]), "+v"(q1[0]), "+v"(q1[1]),
+                       "+v"(q1[2]), "+v"(q1[3]), "+v"(q1[4]), "+v"(q1[5]), "+v"(q1[6]), "+v"(q1[7]), "+v"(qs[0]), "+v"(qs[1]), "+v"(qs[2]), "+v"(qs[3])
+                     :
+                     : "memory");
+        asm volatile("" // (the rest of the ring passes the same point)
+                     : "+v"(q2[0]), "+v"(q2[1]), "+v"(q2[2]), "+v"(q2[3]), "+v"(q2[4]), "+v"(q2[5]), "+v"(q2[6]), "+v"(q2[7]), "+v"(q3[0]), "+v"(q3[1]),
+                       "+v"(q3[2]), "+v"(q3[3]), "+v"(q3[4]), "+v"(q3[5]), "+v"(q3[6]), "+v"(q3[7]), "+v"(qs[4]), "+v"(qs[5]), "+v"(qs[6]), "+v"(qs[7])
+                     :
+                     : "memory");
+    } else {
+        asm volatile("s_waitcnt vmcnt(0)"
+                     : "+v"(ra[0]), "+v"(ra[1]), "+v"(ra[2]), "+v"(ra[3]), "+v"(ra[4]), "+v"(ra[5]), "+v"(ra[6]), "+v"(ra[7]), "+v"(rb[0]), "+v"(rb[1]),
+                       "+v"(rb[2]), "+v"(rb[3]), "+v"(rb[4]), "+v"(rb[5]), "+v"(rb[6]), "+v"(rb[7])
+                     :
+                     : "memory");
+    }
     const int rest = (int)(T - tb); // (the same for the whole workgroup)
     if (rest > 0) step(std::integral_constant<int, 0>{}, std::false_type{}, tb);
     if (rest > 1) step(std::integral_constant<int, 1>{}, std::false_type{}, tb + 1);
@@ -318,13 +379,13 @@ __device__ __forceinline__ void seq_chain_waves(const SeqArgs &a, SeqShared &s, 
 }
 
 // Both kinds of waves pass the same barriers: one after their set-up, one at the end of every step.
-__global__ __launch_bounds__(512) void affine_seq_kernel(SeqArgs a)
+template <bool ADJ> __global__ __launch_bounds__(512) void affine_seq_kernel(SeqArgs a)
 {
     __shared__ __align__(16) SeqShared s;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (wave < 4)
-        seq_matrix_waves(a, s, wave, lane);
+        seq_matrix_waves<ADJ>(a, s, wave, lane);
     else
         seq_chain_waves(a, s, wave - 4, lane);
 }
@@ -332,7 +393,8 @@ __global__ __launch_bounds__(512) void affine_seq_kernel(SeqArgs a)
 } // namespace
 
 // every sequence of the batch by one workgroup, start to end; the caller has checked pointers and sizes
-int launch_affine_seq(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H, void *scaled, void *logscale, long long T, long long batch)
+int launch_affine_seq(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H, void *scaled, void *logscale, long long T, long long batch,
+                      const float *adjoint_shift)
 {
     if (T <= 0 || batch <= 0) return GOOM_OK;
     if (batch > 0x7fffffffLL) return goom::fail(ctx, GOOM_EUNSUPPORTED, "too many sequences for one launch (%lld)", batch);
@@ -343,9 +405,13 @@ int launch_affine_seq(goom_ctx *ctx, const void *A, const void *bias, const void
     args.out_goom = static_cast<unsigned char *>(H);
     args.out_scaled = static_cast<float *>(scaled);
     args.out_logscale = static_cast<float *>(logscale);
+    args.left_shift = adjoint_shift;
     args.T = T;
     goom::prof_begin(ctx, "affine_sequential_walk");
-    hipLaunchKernelGGL(affine_seq_kernel, dim3((unsigned)batch), dim3(512), 0, ctx->stream, args);
+    if (adjoint_shift)
+        hipLaunchKernelGGL(affine_seq_kernel<true>, dim3((unsigned)batch), dim3(512), 0, ctx->stream, args);
+    else
+        hipLaunchKernelGGL(affine_seq_kernel<false>, dim3((unsigned)batch), dim3(512), 0, ctx->stream, args);
     goom::prof_end(ctx);
     return goom::check_hip(ctx, hipGetLastError(), "launch affine_seq_kernel");
 }

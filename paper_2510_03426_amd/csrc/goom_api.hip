@@ -971,9 +971,10 @@ static int run_affine(goom_ctx *ctx, const void *A, const void *bias, const void
     const size_t need = want_scaled ? align_up(ap.total(), 256) + (fused ? 0 : affine_states_bytes(T, d, batch, dtype)) : ap.total();
     if (int s = check_workspace(ctx, ws, ws_bytes, need)) return s;
     if (int s = need_ctx(ctx)) return s;
-    if (affine_sequential_applies(T, d, batch, dtype, opts) && !adjoint_shift && !io_shift)
+    if (affine_sequential_applies(T, d, batch, dtype, opts) && !io_shift)
         // enough sequences to fill the chip one workgroup each: no chunks, every matrix read once
-        return goom_chain::launch_affine_seq(ctx, A, bias, h0, H, want_scaled ? scaled : nullptr, want_scaled ? logscale : nullptr, T, batch);
+        return goom_chain::launch_affine_seq(ctx, A, bias, h0, H, want_scaled ? scaled : nullptr, want_scaled ? logscale : nullptr, T, batch,
+                                             adjoint_shift);
     const size_t cb = 2 * comp_bytes(dtype);
     if (want_scaled && !fused) {
         // the states as GOOMs behind the scan's own workspace, then their scaled exponentials

@@ -204,7 +204,9 @@ namespace goom_chain {
 int launch_replicate_power(goom_ctx *ctx, void *totals, long long stride, int fact_cols, int dp, int d, long long batch,
                            long long chunks, long long chunks_per_item, bool f64);
 // recurrence with bias, float components, d = 32: every sequence walked start to end by one workgroup (goom_affine_seq.hip);
-// H, scaled, logscale: any of the outputs may be NULL
-int launch_affine_seq(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H, void *scaled, void *logscale, long long T, long long batch);
+// H, scaled, logscale: any of the outputs may be NULL; adjoint_shift: NULL, or [batch, T] floats: the factor of step s is then the
+// transpose of matrix T - s (any for s = 0) with adjoint_shift[s] added to its log-magnitudes
+int launch_affine_seq(goom_ctx *ctx, const void *A, const void *bias, const void *h0, void *H, void *scaled, void *logscale, long long T, long long batch,
+                      const float *adjoint_shift);
 } // namespace goom_chain
 

@@ -910,7 +910,9 @@ def test_codec_backward_redefined_derivatives(G, oracle, comp):
     (300, 32, 2, 32, np.complex64, False, 1.05), (1000, 16, 2, 0, np.complex64, True, 1.05), (4000, 32, 1, 0, np.complex64, True, 1.3),
     (64, 8, 3, 9, np.complex64, True, 1.05), (257, 64, 1, 40, np.complex64, False, 1.05), (200, 16, 2, 16, np.complex128, True, 1.05),
     (1, 32, 2, 0, np.complex64, True, 1.05), (40, 128, 1, 8, np.complex128, True, 1.05), (50, 31, 2, 0, np.complex64, False, 1.05),
-    (601, 16, 2, 50, np.complex64, False, 1.05)])
+    (601, 16, 2, 50, np.complex64, False, 1.05),
+    # many sequences of d = 32: the adjoint recurrence walked sequence by sequence, its factors read transposed and in reverse
+    (300, 32, 96, 0, np.complex64, False, 1.05), (37, 32, 100, 0, np.complex64, True, 1.05), (1, 32, 96, 0, np.complex64, True, 1.05)])
 def test_affine_scan_backward(G, oracle, T, d, batch, chunk, ctype, with_h0, gain):
     """Gradients of L = sum grad_h * Re h with respect to the log-magnitudes of A, bias and h0, against the oracle's
     adjoint recurrence fed the same forward states."""
@@ -935,7 +937,7 @@ def test_affine_scan_backward(G, oracle, T, d, batch, chunk, ctype, with_h0, gai
     tol_a = rel * np.abs(wa) + 1e-3 * rel * np.abs(wa).max(axis=(-1, -2), keepdims=True) + 2 * float(np.finfo(comp).tiny)  # (results are reals of the component type; subnormal ones may be flushed)
     tol_b = rel * np.abs(wb) + 1e-3 * rel * np.abs(wb).max(axis=-1, keepdims=True) + 2 * float(np.finfo(comp).tiny)
     sens_a, sens_b = np.zeros_like(wa), np.zeros_like(wb)
-    for _ in range(2):
+    for _ in range(4 if wa.size > 500000 * d else 2):  # (more probes where there are many more entries: see test_affine_scan_matches_oracle)
         pert = lambda z: None if z is None else (z.astype(np.complex128) + eta * rng.standard_normal(z.shape) * np.where(np.isfinite(z.real), 1.0, 0.0))
         pa, pb, _, _ = oracle.affine_scan_backward(pert(Az), pert(bz), Gh, h0=pert(h0), h=pert(H))
         sens_a, sens_b = np.maximum(sens_a, np.abs(pa - wa)), np.maximum(sens_b, np.abs(pb - wb))
