@@ -4,13 +4,14 @@
 // With a hundred sequences or more there is no need to cut a sequence into chunks (whose products cost a matrix-matrix
 // product per step and a second pass over the matrices): a workgroup keeps eight steps of its sequence's matrices in
 // flight, which is enough outstanding memory traffic per compute unit, and a step is a matrix-vector product.  The
-// work of a step falls into a part that does not depend on the running vector and a chain that does, and the eight
+// work of a step falls into a part that does not depend on the running vector and a chain that does, and the
 // waves of the workgroup are split accordingly, one wave of each kind per SIMD, so that the first fills the waits of
-// the second:
+// the second; a ninth wave writes the states out:
 //
 //   * waves 0-3 scale the matrices, one step ahead: a lane loads four adjacent entries of a row (eight lanes a row,
 //     eight rows a wave), the row's lanes agree on its power-of-two shift n_i, and (+-) 2^(log2|A_ij| - n_i) goes to
-//     LDS with n_i.  They also write the states out, taking turns;
+//     LDS with n_i and with what the chain needs of the row's bias (a whole-number exponent at or above its log2
+//     magnitude, its log-magnitude, its sign bit);
 //   * waves 4-7 run the chain: the vector lives in LDS as float mantissas with one whole-number exponent per group of
 //     eight entries (the rows one wave produces); a lane reads four scaled entries of its row and its four entries of
 //     the vector, brings these to the largest group exponent G, and the row's eight lanes add up their products: entry
@@ -18,8 +19,9 @@
 //     largest of the eight sums' and the eight bias terms' exponents), the wave writes eight mantissas and that exponent.
 //
 // One workgroup barrier ends a step: scaled matrices, mantissas and exponents alternate between two sets of LDS words.
-// The state of step t - 1 leaves during step t: as a GOOM, and / or as the scaled exponential of Section 4.3, eq. 27
-// with its log-scaling constant.  Nothing but A_t, b_t (read once) and the outputs (written once) touches HBM.
+// The state of step t - 1 leaves during step t, through wave 8: as a GOOM, and / or as the scaled exponential of Section 4.3, eq. 27
+// with its log-scaling constant.  Nothing but A_t, b_t (read once) and the outputs (written once) touches HBM; the chain
+// waves touch no memory but LDS.
 #include "goom_chain_fast.h"
 #include <type_traits>
 
@@ -31,6 +33,7 @@ constexpr int kSeqDepth = 8;          // steps of a sequence in flight
 constexpr int kSeqNone = -(1 << 28);  // exponent of a group of zeros
 constexpr int kSeqExpLimit = 1 << 27; // whole-number exponents are kept inside +- this
 constexpr int kSeqD = 32;
+constexpr int kSeqThreads = 9 * 64;    // four waves for the matrices, four for the chain, one for the outputs
 
 struct SeqArgs {
     const unsigned char *A;    // [batch, T, 32, 32] complex64
@@ -45,7 +48,7 @@ struct SeqArgs {
 
 struct SeqShared {
     float sv[2][kSeqD * kSeqD]; // scaled, signed entries of a step's matrix
-    int n[2][kSeqD];            // its row shifts
+    int4 rec[2][kSeqD];         // per row: its shift n_i; the bias's whole-number exponent, log-magnitude (float bits) and sign bit
     float m[2][kSeqD];          // mantissas of the vector
     int f[2][4];                // exponent of entries 8 w .. 8 w + 7 (the rows chain wave w produces)
 };
@@ -64,27 +67,29 @@ __device__ inline void lds_barrier()
 // pass through the wait before their first use, so nothing reads them earlier; a wave's vector-memory loads return in the
 // order of issue, and stores issued in between only make the wait stricter.
 typedef float f2 __attribute__((ext_vector_type(2)));
-__device__ inline void load_matrix_part(f4 &x, f4 &y, const unsigned char *p)
+__device__ inline void load_matrix_part(f4 &x, f4 &y, f2 &b, const unsigned char *p, const unsigned char *pb)
 {
-    asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx4 %1, %2, off offset:16" : "=&v"(x), "=&v"(y) : "v"(p) : "memory");
-}
-// the same four entries of a row of the transpose (source rows 256 bytes apart), and the step's shift
-__device__ inline void load_matrix_part_transposed(f2 &e0, f2 &e1, f2 &e2, f2 &e3, float &sh, const unsigned char *p, const float *ps)
-{
-    asm volatile("global_load_dwordx2 %0, %5, off\n\tglobal_load_dwordx2 %1, %5, off offset:256\n\tglobal_load_dwordx2 %2, %5, off offset:512\n\t"
-                 "global_load_dwordx2 %3, %5, off offset:768\n\tglobal_load_dword %4, %6, off"
-                 : "=&v"(e0), "=&v"(e1), "=&v"(e2), "=&v"(e3), "=&v"(sh)
-                 : "v"(p), "v"(ps)
+    asm volatile("global_load_dwordx4 %0, %3, off\n\tglobal_load_dwordx4 %1, %3, off offset:16\n\tglobal_load_dwordx2 %2, %4, off"
+                 : "=&v"(x), "=&v"(y), "=&v"(b)
+                 : "v"(p), "v"(pb)
                  : "memory");
 }
-template <int NEWER> __device__ inline void wait_matrix_part_transposed(f2 &e0, f2 &e1, f2 &e2, f2 &e3, float &sh)
+// the same four entries of a row of the transpose (source rows 256 bytes apart), and the step's shift
+__device__ inline void load_matrix_part_transposed(f2 &e0, f2 &e1, f2 &e2, f2 &e3, float &sh, f2 &b, const unsigned char *p, const float *ps,
+                                                   const unsigned char *pb)
 {
-    asm volatile("s_waitcnt vmcnt(%5)" : "+v"(e0), "+v"(e1), "+v"(e2), "+v"(e3), "+v"(sh) : "n"(NEWER) : "memory");
+    asm volatile("global_load_dwordx2 %0, %6, off\n\tglobal_load_dwordx2 %1, %6, off offset:256\n\tglobal_load_dwordx2 %2, %6, off offset:512\n\t"
+                 "global_load_dwordx2 %3, %6, off offset:768\n\tglobal_load_dword %4, %7, off\n\tglobal_load_dwordx2 %5, %8, off"
+                 : "=&v"(e0), "=&v"(e1), "=&v"(e2), "=&v"(e3), "=&v"(sh), "=&v"(b)
+                 : "v"(p), "v"(ps), "v"(pb)
+                 : "memory");
 }
-__device__ inline void load_bias_entry(f2 &b, const unsigned char *p) { asm volatile("global_load_dwordx2 %0, %1, off" : "=&v"(b) : "v"(p) : "memory"); }
 // what was issued kSeqDepth steps ago has landed once at most NEWER younger loads are outstanding
-template <int NEWER> __device__ inline void wait_matrix_part(f4 &x, f4 &y) { asm volatile("s_waitcnt vmcnt(%2)" : "+v"(x), "+v"(y) : "n"(NEWER) : "memory"); }
-template <int NEWER> __device__ inline void wait_bias_entry(f2 &b) { asm volatile("s_waitcnt vmcnt(%1)" : "+v"(b) : "n"(NEWER) : "memory"); }
+template <int NEWER> __device__ inline void wait_matrix_part_transposed(f2 &e0, f2 &e1, f2 &e2, f2 &e3, float &sh, f2 &b)
+{
+    asm volatile("s_waitcnt vmcnt(%6)" : "+v"(e0), "+v"(e1), "+v"(e2), "+v"(e3), "+v"(sh), "+v"(b) : "n"(NEWER) : "memory");
+}
+template <int NEWER> __device__ inline void wait_matrix_part(f4 &x, f4 &y, f2 &b) { asm volatile("s_waitcnt vmcnt(%3)" : "+v"(x), "+v"(y), "+v"(b) : "n"(NEWER) : "memory"); }
 
 constexpr float kSeqHi = 1.44269502162933349609375f; // float nearest log2(e)
 constexpr float kSeqLo = 1.925963033500011e-8f;      // log2(e) - kSeqHi
@@ -114,35 +119,32 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
     const size_t item = blockIdx.x;
     const int row = 8 * wave + (lane >> 3); // eight lanes a row
     const int cq = lane & 7;                // the lane's columns: 4 cq .. 4 cq + 3
-    const int ent = lane & 31;              // entry handled when this wave writes a state out
     const unsigned char *Ap = a.A + item * (size_t)T * (D * D * 8) + (ADJ ? (size_t)(4 * cq * D + row) * 8 : (size_t)(row * D + 4 * cq) * 8);
     [[maybe_unused]] const float *shp = ADJ ? a.left_shift + item * (size_t)T : nullptr;
-    unsigned char *og = a.out_goom ? a.out_goom + item * (size_t)T * (D * 8) + (size_t)ent * 8 : nullptr;
-    float *os = a.out_scaled ? a.out_scaled + item * (size_t)T * D + ent : nullptr;
-    float *ol = a.out_logscale ? a.out_logscale + item * (size_t)T : nullptr;
-    const float kNegInf = -__builtin_huge_valf();
+    const unsigned char *bp = a.bias + item * (size_t)T * (D * 8) + (size_t)row * 8;
 
     // slot j mod kSeqDepth: the lane's four entries of the factor of step j (and, transposed, its shift)
     [[maybe_unused]] f4 ra[kSeqDepth], rb[kSeqDepth];
     [[maybe_unused]] f2 q0[kSeqDepth], q1[kSeqDepth], q2[kSeqDepth], q3[kSeqDepth];
     [[maybe_unused]] float qs[kSeqDepth];
-    constexpr int kNewer = (ADJ ? 5 : 2) * (kSeqDepth - 1); // loads issued after a slot's own until its turn comes again
+    f2 bq[kSeqDepth]; // the row's bias of step j
+    constexpr int kNewer = (ADJ ? 6 : 3) * (kSeqDepth - 1); // loads issued after a slot's own until its turn comes again
     auto load_slot = [&](auto sc, long long j) { // factor of step j (past the end: the last one again)
         constexpr int k = decltype(sc)::value;
         const long long jj = j < T ? j : T - 1;
         if constexpr (ADJ) {
             const long long src = jj > 0 ? T - jj : T - 1;
-            load_matrix_part_transposed(q0[k], q1[k], q2[k], q3[k], qs[k], Ap + (size_t)src * (D * D * 8), shp + jj);
+            load_matrix_part_transposed(q0[k], q1[k], q2[k], q3[k], qs[k], bq[k], Ap + (size_t)src * (D * D * 8), shp + jj, bp + (size_t)jj * (D * 8));
         } else {
-            load_matrix_part(ra[k], rb[k], Ap + (size_t)jj * (D * D * 8));
+            load_matrix_part(ra[k], rb[k], bq[k], Ap + (size_t)jj * (D * D * 8), bp + (size_t)jj * (D * 8));
         }
     };
     auto wait_slot = [&](auto sc) {
         constexpr int k = decltype(sc)::value;
         if constexpr (ADJ)
-            wait_matrix_part_transposed<kNewer>(q0[k], q1[k], q2[k], q3[k], qs[k]);
+            wait_matrix_part_transposed<kNewer>(q0[k], q1[k], q2[k], q3[k], qs[k], bq[k]);
         else
-            wait_matrix_part<kNewer>(ra[k], rb[k]);
+            wait_matrix_part<kNewer>(ra[k], rb[k], bq[k]);
     };
     load_slot(std::integral_constant<int, 0>{}, 0);
     load_slot(std::integral_constant<int, 1>{}, 1);
@@ -187,30 +189,11 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
             sv[e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) | (__builtin_bit_cast(int, kf) << 31));
         }
         *reinterpret_cast<f4 *>(&s.sv[set][row * D + 4 * cq]) = sv;
-        if (cq == 0) s.n[set][row] = (int)nf;
-    };
-
-    // the state held in LDS set `set` (that of step t) leaves through this wave's lanes
-    auto write_state = [&](int set, long long t) {
-        const float m = s.m[set][ent];
-        const int f = s.f[set][ent >> 3];
-        if (og) {
-            float2 o;
-            o.x = C::out_re_f(m, (float)f); // (-inf for a zero)
-            o.y = m < 0.0f ? C::pi() : 0.0f;
-            if (lane < D) *reinterpret_cast<float2 *>(og + (size_t)t * (D * 8)) = o;
-        }
-        if (os || ol) {
-            // scaled exponentiation (Section 4.3, eq. 27): with c the log of the largest magnitude, exp(z_i - c + 2) is the entry over the
-            // largest entry, times e^2; the exponents only enter c
-            const int4 fa = *reinterpret_cast<const int4 *>(&s.f[set][0]);
-            const int g = C::imax(C::imax(fa.x, fa.y), C::imax(fa.z, fa.w));
-            const int down = f - g;
-            const float v = __builtin_ldexpf(m, down > -300 ? down : -300);
-            float am = __builtin_fabsf(v);
-            am = C::group_allmax<32>(am, am);
-            if (os && lane < D) os[(size_t)t * D] = am > 0.0f ? v * (7.38905609893065022723f / am) : 0.0f;
-            if (ol && lane == 0) ol[t] = am > 0.0f ? (float)(((double)C::log2_abs(am) + (double)g) * 0.693147180559945309417) : kNegInf;
+        if (cq == 0) {
+            // what the chain needs of the row and of its bias, in one 16-byte word
+            const f2 b = bq[k];
+            const float kf = __builtin_fmaf(b[1], 0.318309886183790671538f, 12582912.0f);
+            s.rec[set][row] = int4{(int)nf, exponent_above(b[0]), __builtin_bit_cast(int, b[0]), __builtin_bit_cast(int, kf) << 31};
         }
     };
 
@@ -220,13 +203,12 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
     load_slot(std::integral_constant<int, 0>{}, kSeqDepth);
     lds_barrier();
 
-    // while the chain takes step t: the state of step t - 1 out, matrix t + 1 scaled.  u = t mod kSeqDepth picks the ring's
+    // while the chain takes step t: the factor of step t + 1 scaled.  u = t mod kSeqDepth picks the ring's
     // registers and the LDS sets at compile time
-    auto step = [&](auto uc, auto prefetch, long long t) {
+    auto step = [&](auto uc, auto prefetch, [[maybe_unused]] long long t) {
         constexpr int u = decltype(uc)::value;
         constexpr bool kPrefetch = decltype(prefetch)::value; // false after the last full round: the rest of the sequence has landed
         constexpr int slot = (u + 1) % kSeqDepth;
-        if (t > 0 && wave == (u & 3)) write_state((u + 1) & 1, t - 1);
         if constexpr (kPrefetch) wait_slot(std::integral_constant<int, slot>{});
         scale_rows(std::integral_constant<int, slot>{}, (u + 1) & 1); // (past the end: the last factor again, read by nobody)
         // the registers are free: the factor of step t + 1 + kSeqDepth (every step of a full round issues its loads)
@@ -255,13 +237,15 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
                      : "memory");
         asm volatile("" // (the rest of the ring passes the same point)
                      : "+v"(q2[0]), "+v"(q2[1]), "+v"(q2[2]), "+v"(q2[3]), "+v"(q2[4]), "+v"(q2[5]), "+v"(q2[6]), "+v"(q2[7]), "+v"(q3[0]), "+v"(q3[1]),
-                       "+v"(q3[2]), "+v"(q3[3]), "+v"(q3[4]), "+v"(q3[5]), "+v"(q3[6]), "+v"(q3[7]), "+v"(qs[4]), "+v"(qs[5]), "+v"(qs[6]), "+v"(qs[7])
+                       "+v"(q3[2]), "+v"(q3[3]), "+v"(q3[4]), "+v"(q3[5]), "+v"(q3[6]), "+v"(q3[7]), "+v"(qs[4]), "+v"(qs[5]), "+v"(qs[6]), "+v"(qs[7]),
+                       "+v"(bq[0]), "+v"(bq[1]), "+v"(bq[2]), "+v"(bq[3]), "+v"(bq[4]), "+v"(bq[5]), "+v"(bq[6]), "+v"(bq[7])
                      :
                      : "memory");
     } else {
         asm volatile("s_waitcnt vmcnt(0)"
                      : "+v"(ra[0]), "+v"(ra[1]), "+v"(ra[2]), "+v"(ra[3]), "+v"(ra[4]), "+v"(ra[5]), "+v"(ra[6]), "+v"(ra[7]), "+v"(rb[0]), "+v"(rb[1]),
-                       "+v"(rb[2]), "+v"(rb[3]), "+v"(rb[4]), "+v"(rb[5]), "+v"(rb[6]), "+v"(rb[7])
+                       "+v"(rb[2]), "+v"(rb[3]), "+v"(rb[4]), "+v"(rb[5]), "+v"(rb[6]), "+v"(rb[7]), "+v"(bq[0]), "+v"(bq[1]), "+v"(bq[2]), "+v"(bq[3]),
+                       "+v"(bq[4]), "+v"(bq[5]), "+v"(bq[6]), "+v"(bq[7])
                      :
                      : "memory");
     }
@@ -273,7 +257,6 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
     if (rest > 4) step(std::integral_constant<int, 4>{}, std::false_type{}, tb + 4);
     if (rest > 5) step(std::integral_constant<int, 5>{}, std::false_type{}, tb + 5);
     if (rest > 6) step(std::integral_constant<int, 6>{}, std::false_type{}, tb + 6);
-    if (wave == 0) write_state((int)((T - 1) & 1), T - 1);
 }
 
 // ---- waves 4-7: the chain
@@ -286,15 +269,8 @@ __device__ __forceinline__ void seq_chain_waves(const SeqArgs &a, SeqShared &s, 
     const int row = 8 * kw + (lane >> 3);
     const int cq = lane & 7;
     const int src_group = cq >> 1; // the group the lane's four entries of the vector belong to
-    const unsigned char *bp = a.bias + item * (size_t)T * (D * 8) + (size_t)row * 8;
     const float kNegInf = -__builtin_huge_valf();
 
-    f2 br[kSeqDepth]; // slot t mod kSeqDepth: the row's bias of step t
-#pragma unroll
-    for (int u = 0; u < kSeqDepth; ++u) {
-        const long long t = u < T ? u : T - 1;
-        load_bias_entry(br[u], bp + (size_t)t * (D * 8));
-    }
     // the starting vector goes to the set of LDS words that step 0 reads
     if (kw == 0) {
         const int ent = lane & 31;
@@ -309,19 +285,17 @@ __device__ __forceinline__ void seq_chain_waves(const SeqArgs &a, SeqShared &s, 
     }
     lds_barrier();
 
-    auto step = [&](auto uc, auto prefetch, long long t) {
+    auto step = [&](auto uc, auto, long long) {
         constexpr int u = decltype(uc)::value;
-        constexpr bool kPrefetch = decltype(prefetch)::value;
         constexpr int rs = (u + 1) & 1, ws = u & 1; // sets of the vector read and written (tb is a multiple of the depth, which is even)
         constexpr int ms = u & 1;                   // set of the scaled matrix
         const f4 sv = *reinterpret_cast<const f4 *>(&s.sv[ms][row * D + 4 * cq]);
-        const int n = s.n[ms][row];
+        const int4 rec = s.rec[ms][row]; // the row's shift; its bias: exponent, log-magnitude, sign
+        const int n = rec.x, eb = rec.y;
+        const float bre = __builtin_bit_cast(float, rec.z);
         const f4 hm = *reinterpret_cast<const f4 *>(&s.m[rs][4 * cq]);
         const int fsrc = s.f[rs][src_group];
         const int4 fa = *reinterpret_cast<const int4 *>(&s.f[rs][0]);
-        if constexpr (kPrefetch) wait_bias_entry<kSeqDepth - 1>(br[u]);
-        const f2 b = br[u];
-        const int eb = exponent_above(b[0]);
         // ---- row i of A_t h_{t-1}: the eight lanes' products on the exponent n_i + G
         const int G = C::imax(C::imax(fa.x, fa.y), C::imax(fa.z, fa.w));
         const int down = fsrc - G;
@@ -340,17 +314,15 @@ __device__ __forceinline__ void seq_chain_waves(const SeqArgs &a, SeqShared &s, 
         F = C::imax(F, C::dpp<0x140>(F)); // the other row in these sixteen lanes
         F = C::xor16_imax(F);
         F = C::xor32_imax(F);
-        F = F > kSeqNone ? (F < 2 * kSeqExpLimit ? F : 2 * kSeqExpLimit) : kSeqNone; // (float log-magnitudes resolve nothing out there)
+        F = F < kSeqNone ? kSeqNone : (F > 2 * kSeqExpLimit ? 2 * kSeqExpLimit : F); // (float log-magnitudes resolve nothing out there)
         const int up = n + G - F; // at most 0 for a non-zero sum
         float mant = __builtin_ldexpf(part, up > -300 ? (up < 300 ? up : 300) : -300);
-        mant += scaled_term(b[0], b[1], F); // (a zero bias, log-magnitude -inf, adds 2^-inf = 0)
+        float xb = __builtin_fmaf(bre, kSeqHi, -(float)F); // the bias on that exponent (a zero bias, log-magnitude -inf, adds 2^-inf = 0)
+        xb = __builtin_fmaf(bre, kSeqLo, xb);
+        mant += __builtin_bit_cast(float, __builtin_bit_cast(int, __builtin_amdgcn_exp2f(xb)) | rec.w);
         const bool none = __builtin_amdgcn_ballot_w64(mant != 0.0f) == 0; // a group of zeros carries no exponent
         if (cq == 0) s.m[ws][row] = mant;
         if (lane == 0) s.f[ws][kw] = none ? kSeqNone : F;
-        if constexpr (kPrefetch) {
-            const long long tn = t + kSeqDepth < T ? t + kSeqDepth : T - 1;
-            load_bias_entry(br[u], bp + (size_t)tn * (D * 8));
-        }
         lds_barrier();
     };
     long long tb = 0;
@@ -364,10 +336,6 @@ __device__ __forceinline__ void seq_chain_waves(const SeqArgs &a, SeqShared &s, 
         step(std::integral_constant<int, 6>{}, std::true_type{}, tb + 6);
         step(std::integral_constant<int, 7>{}, std::true_type{}, tb + 7);
     }
-    asm volatile("s_waitcnt vmcnt(0)"
-                 : "+v"(br[0]), "+v"(br[1]), "+v"(br[2]), "+v"(br[3]), "+v"(br[4]), "+v"(br[5]), "+v"(br[6]), "+v"(br[7])
-                 :
-                 : "memory"); // (as in the matrix waves: nothing in flight into registers the last, partial round may reuse)
     const int rest = (int)(T - tb);
     if (rest > 0) step(std::integral_constant<int, 0>{}, std::false_type{}, tb);
     if (rest > 1) step(std::integral_constant<int, 1>{}, std::false_type{}, tb + 1);
@@ -378,16 +346,63 @@ __device__ __forceinline__ void seq_chain_waves(const SeqArgs &a, SeqShared &s, 
     if (rest > 6) step(std::integral_constant<int, 6>{}, std::false_type{}, tb + 6);
 }
 
-// Both kinds of waves pass the same barriers: one after their set-up, one at the end of every step.
-template <bool ADJ> __global__ __launch_bounds__(512) void affine_seq_kernel(SeqArgs a)
+// ---- wave 8: the states out.  While the chain takes step t it reads the state of step t - 1 from LDS and stores it, so that
+// neither the chain nor the matrix waves ever wait for a logarithm or a store.
+__device__ __forceinline__ void seq_output_wave(const SeqArgs &a, SeqShared &s, int lane)
+{
+    typedef Comp<float> C;
+    constexpr int D = kSeqD;
+    const long long T = a.T;
+    const size_t item = blockIdx.x;
+    const int ent = lane & 31; // the entry this lane handles (the upper half of the wave repeats the lower and stores nothing)
+    unsigned char *og = a.out_goom ? a.out_goom + item * (size_t)T * (D * 8) + (size_t)ent * 8 : nullptr;
+    float *os = a.out_scaled ? a.out_scaled + item * (size_t)T * D + ent : nullptr;
+    float *ol = a.out_logscale ? a.out_logscale + item * (size_t)T : nullptr;
+    const float kNegInf = -__builtin_huge_valf();
+    // the state held in LDS set `set` (that of step t)
+    auto write_state = [&](int set, long long t) {
+        const float m = s.m[set][ent];
+        const int f = s.f[set][ent >> 3];
+        if (og) {
+            float2 o;
+            o.x = C::out_re_f(m, (float)f); // (-inf for a zero)
+            o.y = m < 0.0f ? C::pi() : 0.0f;
+            if (lane < D) *reinterpret_cast<float2 *>(og + (size_t)t * (D * 8)) = o;
+        }
+        if (os || ol) {
+            // scaled exponentiation (Section 4.3, eq. 27): with c the log of the largest magnitude, exp(z_i - c + 2) is the entry over the
+            // largest entry, times e^2; the exponents only enter c
+            const int4 fa = *reinterpret_cast<const int4 *>(&s.f[set][0]);
+            const int g = C::imax(C::imax(fa.x, fa.y), C::imax(fa.z, fa.w));
+            const int down = f - g;
+            const float v = __builtin_ldexpf(m, down > -300 ? down : -300);
+            float am = __builtin_fabsf(v);
+            am = C::group_allmax<32>(am, am);
+            if (os && lane < D) os[(size_t)t * D] = am > 0.0f ? v * (7.38905609893065022723f * __builtin_amdgcn_rcpf(am)) : 0.0f;
+            if (ol && lane == 0) ol[t] = am > 0.0f ? (float)(((double)C::log2_abs(am) + (double)g) * 0.693147180559945309417) : kNegInf;
+        }
+    };
+
+    lds_barrier(); // the set-up of the other waves
+    for (long long t = 0; t < T; ++t) {
+        if (t > 0) write_state((int)((t + 1) & 1), t - 1);
+        lds_barrier();
+    }
+    write_state((int)((T - 1) & 1), T - 1);
+}
+
+// All three kinds of waves pass the same barriers: one after their set-up, one at the end of every step.
+template <bool ADJ> __global__ __launch_bounds__(kSeqThreads) void affine_seq_kernel(SeqArgs a)
 {
     __shared__ __align__(16) SeqShared s;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (wave < 4)
         seq_matrix_waves<ADJ>(a, s, wave, lane);
-    else
+    else if (wave < 8)
         seq_chain_waves(a, s, wave - 4, lane);
+    else
+        seq_output_wave(a, s, lane);
 }
 
 } // namespace
@@ -409,9 +424,9 @@ int launch_affine_seq(goom_ctx *ctx, const void *A, const void *bias, const void
     args.T = T;
     goom::prof_begin(ctx, "affine_sequential_walk");
     if (adjoint_shift)
-        hipLaunchKernelGGL(affine_seq_kernel<true>, dim3((unsigned)batch), dim3(512), 0, ctx->stream, args);
+        hipLaunchKernelGGL(affine_seq_kernel<true>, dim3((unsigned)batch), dim3(kSeqThreads), 0, ctx->stream, args);
     else
-        hipLaunchKernelGGL(affine_seq_kernel<false>, dim3((unsigned)batch), dim3(512), 0, ctx->stream, args);
+        hipLaunchKernelGGL(affine_seq_kernel<false>, dim3((unsigned)batch), dim3(kSeqThreads), 0, ctx->stream, args);
     goom::prof_end(ctx);
     return goom::check_hip(ctx, hipGetLastError(), "launch affine_seq_kernel");
 }
