@@ -912,8 +912,8 @@ static AffinePlan plan_affine(long long T, int d, long long batch, int dtype, co
 }
 
 // Batches of many sequences with a matrix per step (float components, d = 32, default chunking): each sequence is walked start
-// to end by one workgroup, which takes about 0.3 us a step whatever the batch (up to one workgroup per compute unit); the chunked
-// scan takes about 3.8 ns a token, so the walk wins from about 80 sequences on.
+// to end by one workgroup, which takes about 0.27 us a step whatever the batch (up to one workgroup per compute unit); the chunked
+// scan takes about 3.8 ns a token, so the walk wins from about 75 sequences on.
 constexpr long long kAffineSequentialMinBatch = 96;
 static bool affine_sequential_applies(long long T, int d, long long batch, int dtype, const goom_scan_opts *opts)
 {
