@@ -582,12 +582,14 @@ def recurrence(g, torch, dev, si):
     gh = torch.randn((nseq, T, d), device=dev, generator=si.device_generator(251003426 * 10 + 53, dev))
     fn = lambda: g.affine_scan_backward(az, bz, h, gh)
     sec = timed(torch, fn, 2)
-    # algorithmic bytes: A read twice by the adjoint scan (transposed, in place), read again for its gradient (reals),
-    # which is written
-    bbytes = az.numel() * (8 * 3 + 4)
+    kms = kernel_times(g, fn)
+    # algorithmic bytes: A read by the adjoint recurrence (transposed, in place; twice where that runs as a chunked scan), read
+    # again for its gradient (reals), which is written
+    reads = 2 if "affine_sequential_walk" in kms else 3
+    bbytes = az.numel() * (8 * reads + 4)
     res["recurrence_backward_128seq_T65536_d32"] = {
         "ms": round(sec * 1e3, 3), "tokens_per_s": round(nseq * T / sec, 1), "hbm_gbs_algorithmic": round(bbytes / sec / 1e9, 1),
-        "kernels_ms": kernel_times(g, fn)}
+        "passes_over_the_matrices": reads, "kernels_ms": kms}
     del h, gh
     g._ws = None
     torch.cuda.empty_cache()

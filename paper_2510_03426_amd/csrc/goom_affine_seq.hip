@@ -47,7 +47,8 @@ struct SeqArgs {
 };
 
 struct SeqShared {
-    float sv[2][kSeqD * kSeqD]; // scaled, signed entries of a step's matrix
+    float sv[2][kSeqD * (kSeqD + 1)]; // scaled, signed entries of a step's matrix (adjoint recurrence: rows one word apart more, read by columns)
+    int nsrc[2][kSeqD];               // adjoint recurrence: the row shifts of the matrix as stored (they go with the vector's entries)
     int4 rec[2][kSeqD];         // per row: its shift n_i; the bias's whole-number exponent, log-magnitude (float bits) and sign bit
     float m[2][kSeqD];          // mantissas of the vector
     int f[2][4];                // exponent of entries 8 w .. 8 w + 7 (the rows chain wave w produces)
@@ -74,20 +75,19 @@ __device__ inline void load_matrix_part(f4 &x, f4 &y, f2 &b, const unsigned char
                  : "v"(p), "v"(pb)
                  : "memory");
 }
-// the same four entries of a row of the transpose (source rows 256 bytes apart), and the step's shift
-__device__ inline void load_matrix_part_transposed(f2 &e0, f2 &e1, f2 &e2, f2 &e3, float &sh, f2 &b, const unsigned char *p, const float *ps,
-                                                   const unsigned char *pb)
+// the same with the step's shift (adjoint recurrence)
+__device__ inline void load_matrix_part_shift(f4 &x, f4 &y, f2 &b, float &sh, const unsigned char *p, const unsigned char *pb, const float *ps)
 {
-    asm volatile("global_load_dwordx2 %0, %6, off\n\tglobal_load_dwordx2 %1, %6, off offset:256\n\tglobal_load_dwordx2 %2, %6, off offset:512\n\t"
-                 "global_load_dwordx2 %3, %6, off offset:768\n\tglobal_load_dword %4, %7, off\n\tglobal_load_dwordx2 %5, %8, off"
-                 : "=&v"(e0), "=&v"(e1), "=&v"(e2), "=&v"(e3), "=&v"(sh), "=&v"(b)
-                 : "v"(p), "v"(ps), "v"(pb)
+    asm volatile("global_load_dwordx4 %0, %4, off\n\tglobal_load_dwordx4 %1, %4, off offset:16\n\tglobal_load_dwordx2 %2, %5, off\n\t"
+                 "global_load_dword %3, %6, off"
+                 : "=&v"(x), "=&v"(y), "=&v"(b), "=&v"(sh)
+                 : "v"(p), "v"(pb), "v"(ps)
                  : "memory");
 }
 // what was issued kSeqDepth steps ago has landed once at most NEWER younger loads are outstanding
-template <int NEWER> __device__ inline void wait_matrix_part_transposed(f2 &e0, f2 &e1, f2 &e2, f2 &e3, float &sh, f2 &b)
+template <int NEWER> __device__ inline void wait_matrix_part_shift(f4 &x, f4 &y, f2 &b, float &sh)
 {
-    asm volatile("s_waitcnt vmcnt(%6)" : "+v"(e0), "+v"(e1), "+v"(e2), "+v"(e3), "+v"(sh), "+v"(b) : "n"(NEWER) : "memory");
+    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(x), "+v"(y), "+v"(b), "+v"(sh) : "n"(NEWER) : "memory");
 }
 template <int NEWER> __device__ inline void wait_matrix_part(f4 &x, f4 &y, f2 &b) { asm volatile("s_waitcnt vmcnt(%3)" : "+v"(x), "+v"(y), "+v"(b) : "n"(NEWER) : "memory"); }
 
@@ -110,7 +110,9 @@ __device__ inline float scaled_term(float re, float im, int f)
 
 // ---- waves 0-3: the matrices, one step ahead of the chain, and the outputs
 // ADJ: the adjoint recurrence's factors, read from the forward pass's matrices: step s takes the transpose of matrix T - s (any
-// matrix for s = 0) and adds left_shift[s] to its log-magnitudes (-inf: a zero matrix).
+// matrix for s = 0) and adds left_shift[s] to its log-magnitudes (-inf: a zero matrix).  The matrix is loaded and scaled as it is
+// stored, row by row (the same contiguous loads as in the forward pass); the chain reads it by columns, and the shift of a stored
+// row j goes with entry j of the vector.
 template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqArgs &a, SeqShared &s, int wave, int lane)
 {
     typedef Comp<float> C;
@@ -119,22 +121,21 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
     const size_t item = blockIdx.x;
     const int row = 8 * wave + (lane >> 3); // eight lanes a row
     const int cq = lane & 7;                // the lane's columns: 4 cq .. 4 cq + 3
-    const unsigned char *Ap = a.A + item * (size_t)T * (D * D * 8) + (ADJ ? (size_t)(4 * cq * D + row) * 8 : (size_t)(row * D + 4 * cq) * 8);
+    const unsigned char *Ap = a.A + item * (size_t)T * (D * D * 8) + (size_t)(row * D + 4 * cq) * 8;
     [[maybe_unused]] const float *shp = ADJ ? a.left_shift + item * (size_t)T : nullptr;
     const unsigned char *bp = a.bias + item * (size_t)T * (D * 8) + (size_t)row * 8;
 
-    // slot j mod kSeqDepth: the lane's four entries of the factor of step j (and, transposed, its shift)
-    [[maybe_unused]] f4 ra[kSeqDepth], rb[kSeqDepth];
-    [[maybe_unused]] f2 q0[kSeqDepth], q1[kSeqDepth], q2[kSeqDepth], q3[kSeqDepth];
+    // slot j mod kSeqDepth: the lane's four entries of the matrix of step j (and, for the adjoint recurrence, the step's shift)
+    f4 ra[kSeqDepth], rb[kSeqDepth];
     [[maybe_unused]] float qs[kSeqDepth];
-    f2 bq[kSeqDepth]; // the row's bias of step j
-    constexpr int kNewer = (ADJ ? 6 : 3) * (kSeqDepth - 1); // loads issued after a slot's own until its turn comes again
+    f2 bq[kSeqDepth]; // the bias of step j, entry `row`
+    constexpr int kNewer = (ADJ ? 4 : 3) * (kSeqDepth - 1); // loads issued after a slot's own until its turn comes again
     auto load_slot = [&](auto sc, long long j) { // factor of step j (past the end: the last one again)
         constexpr int k = decltype(sc)::value;
         const long long jj = j < T ? j : T - 1;
         if constexpr (ADJ) {
             const long long src = jj > 0 ? T - jj : T - 1;
-            load_matrix_part_transposed(q0[k], q1[k], q2[k], q3[k], qs[k], bq[k], Ap + (size_t)src * (D * D * 8), shp + jj, bp + (size_t)jj * (D * 8));
+            load_matrix_part_shift(ra[k], rb[k], bq[k], qs[k], Ap + (size_t)src * (D * D * 8), bp + (size_t)jj * (D * 8), shp + jj);
         } else {
             load_matrix_part(ra[k], rb[k], bq[k], Ap + (size_t)jj * (D * D * 8), bp + (size_t)jj * (D * 8));
         }
@@ -142,7 +143,7 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
     auto wait_slot = [&](auto sc) {
         constexpr int k = decltype(sc)::value;
         if constexpr (ADJ)
-            wait_matrix_part_transposed<kNewer>(q0[k], q1[k], q2[k], q3[k], qs[k], bq[k]);
+            wait_matrix_part_shift<kNewer>(ra[k], rb[k], bq[k], qs[k]);
         else
             wait_matrix_part<kNewer>(ra[k], rb[k], bq[k]);
     };
@@ -158,18 +159,12 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
     // the lane's four entries scaled by the row's power of two and signed, to LDS set `set`
     auto scale_rows = [&](auto sc, int set) {
         constexpr int k = decltype(sc)::value;
-        float re[4], im[4];
+        const f4 x = ra[k], y = rb[k];
+        float re[4] = {x[0], x[2], y[0], y[2]};
+        const float im[4] = {x[1], x[3], y[1], y[3]};
         if constexpr (ADJ) {
-            const f2 q[4] = {q0[k], q1[k], q2[k], q3[k]};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                re[e] = q[e][0] + qs[k];
-                im[e] = q[e][1];
-            }
-        } else {
-            const f4 x = ra[k], y = rb[k];
-            re[0] = x[0], re[1] = x[2], re[2] = y[0], re[3] = y[2];
-            im[0] = x[1], im[1] = x[3], im[2] = y[1], im[3] = y[3];
+            for (int e = 0; e < 4; ++e) re[e] += qs[k];
         }
         int key = C::key_of(vmax_raw(vmax_raw(re[0], re[1]), vmax_raw(re[2], re[3])) * kSeqHi);
         key = C::imax(key, C::dpp<0xB1>(key));
@@ -188,12 +183,19 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
             const float kf = __builtin_fmaf(im[e], 0.318309886183790671538f, 12582912.0f);
             sv[e] = __builtin_bit_cast(float, __builtin_bit_cast(int, v) | (__builtin_bit_cast(int, kf) << 31));
         }
-        *reinterpret_cast<f4 *>(&s.sv[set][row * D + 4 * cq]) = sv;
+        if constexpr (ADJ) {
+            // (rows 33 words apart: the chain's reads by columns then fall on different banks)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s.sv[set][row * (D + 1) + 4 * cq + e] = sv[e];
+        } else {
+            *reinterpret_cast<f4 *>(&s.sv[set][row * D + 4 * cq]) = sv;
+        }
         if (cq == 0) {
             // what the chain needs of the row and of its bias, in one 16-byte word
             const f2 b = bq[k];
             const float kf = __builtin_fmaf(b[1], 0.318309886183790671538f, 12582912.0f);
             s.rec[set][row] = int4{(int)nf, exponent_above(b[0]), __builtin_bit_cast(int, b[0]), __builtin_bit_cast(int, kf) << 31};
+            if constexpr (ADJ) s.nsrc[set][row] = zero_row ? -kSeqExpLimit : (int)nf; // (a zero row must not set the scale of the vector)
         }
     };
 
@@ -229,26 +231,17 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
     }
     // Everything still in flight lands before the last, partial round: from here on the compiler is free to reuse a ring register
     // that no step reads any more, and a load still on its way would overwrite whatever it put there.
-    if constexpr (ADJ) {
-        asm volatile("s_waitcnt vmcnt(0)"
-                     : "+v"(q0[0]), "+v"(q0[1]), "+v"(q0[2]), "+v"(q0[3]), "+v"(q0[4]), "+v"(q0[5]), "+v"(q0[6]), "+v"(q0[7]), "+v"(q1[0]), "+v"(q1[1]),
-                       "+v"(q1[2]), "+v"(q1[3]), "+v"(q1[4]), "+v"(q1[5]), "+v"(q1[6]), "+v"(q1[7]), "+v"(qs[0]), "+v"(qs[1]), "+v"(qs[2]), "+v"(qs[3])
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(ra[0]), "+v"(ra[1]), "+v"(ra[2]), "+v"(ra[3]), "+v"(ra[4]), "+v"(ra[5]), "+v"(ra[6]), "+v"(ra[7]), "+v"(rb[0]), "+v"(rb[1]),
+                   "+v"(rb[2]), "+v"(rb[3]), "+v"(rb[4]), "+v"(rb[5]), "+v"(rb[6]), "+v"(rb[7]), "+v"(bq[0]), "+v"(bq[1]), "+v"(bq[2]), "+v"(bq[3]),
+                   "+v"(bq[4]), "+v"(bq[5]), "+v"(bq[6]), "+v"(bq[7])
+                 :
+                 : "memory");
+    if constexpr (ADJ)
+        asm volatile("" // (the shifts pass the same point)
+                     : "+v"(qs[0]), "+v"(qs[1]), "+v"(qs[2]), "+v"(qs[3]), "+v"(qs[4]), "+v"(qs[5]), "+v"(qs[6]), "+v"(qs[7])
                      :
                      : "memory");
-        asm volatile("" // (the rest of the ring passes the same point)
-                     : "+v"(q2[0]), "+v"(q2[1]), "+v"(q2[2]), "+v"(q2[3]), "+v"(q2[4]), "+v"(q2[5]), "+v"(q2[6]), "+v"(q2[7]), "+v"(q3[0]), "+v"(q3[1]),
-                       "+v"(q3[2]), "+v"(q3[3]), "+v"(q3[4]), "+v"(q3[5]), "+v"(q3[6]), "+v"(q3[7]), "+v"(qs[4]), "+v"(qs[5]), "+v"(qs[6]), "+v"(qs[7]),
-                       "+v"(bq[0]), "+v"(bq[1]), "+v"(bq[2]), "+v"(bq[3]), "+v"(bq[4]), "+v"(bq[5]), "+v"(bq[6]), "+v"(bq[7])
-                     :
-                     : "memory");
-    } else {
-        asm volatile("s_waitcnt vmcnt(0)"
-                     : "+v"(ra[0]), "+v"(ra[1]), "+v"(ra[2]), "+v"(ra[3]), "+v"(ra[4]), "+v"(ra[5]), "+v"(ra[6]), "+v"(ra[7]), "+v"(rb[0]), "+v"(rb[1]),
-                       "+v"(rb[2]), "+v"(rb[3]), "+v"(rb[4]), "+v"(rb[5]), "+v"(rb[6]), "+v"(rb[7]), "+v"(bq[0]), "+v"(bq[1]), "+v"(bq[2]), "+v"(bq[3]),
-                       "+v"(bq[4]), "+v"(bq[5]), "+v"(bq[6]), "+v"(bq[7])
-                     :
-                     : "memory");
-    }
     const int rest = (int)(T - tb); // (the same for the whole workgroup)
     if (rest > 0) step(std::integral_constant<int, 0>{}, std::false_type{}, tb);
     if (rest > 1) step(std::integral_constant<int, 1>{}, std::false_type{}, tb + 1);
@@ -260,7 +253,9 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
 }
 
 // ---- waves 4-7: the chain
-__device__ __forceinline__ void seq_chain_waves(const SeqArgs &a, SeqShared &s, int kw, int lane)
+// ADJ: the step's matrix lies in LDS as it is stored, each row j scaled by its own shift n_j, and is applied transposed: entry i of the
+// product is the sum over j of (entry (j, i)) (entry j of the vector) 2^(n_j), so n_j joins the exponent of entry j of the vector.
+template <bool ADJ> __device__ __forceinline__ void seq_chain_waves(const SeqArgs &a, SeqShared &s, int kw, int lane)
 {
     typedef Comp<float> C;
     constexpr int D = kSeqD;
@@ -289,21 +284,45 @@ __device__ __forceinline__ void seq_chain_waves(const SeqArgs &a, SeqShared &s, 
         constexpr int u = decltype(uc)::value;
         constexpr int rs = (u + 1) & 1, ws = u & 1; // sets of the vector read and written (tb is a multiple of the depth, which is even)
         constexpr int ms = u & 1;                   // set of the scaled matrix
-        const f4 sv = *reinterpret_cast<const f4 *>(&s.sv[ms][row * D + 4 * cq]);
         const int4 rec = s.rec[ms][row]; // the row's shift; its bias: exponent, log-magnitude, sign
-        const int n = rec.x, eb = rec.y;
+        const int eb = rec.y;
         const float bre = __builtin_bit_cast(float, rec.z);
         const f4 hm = *reinterpret_cast<const f4 *>(&s.m[rs][4 * cq]);
         const int fsrc = s.f[rs][src_group];
-        const int4 fa = *reinterpret_cast<const int4 *>(&s.f[rs][0]);
-        // ---- row i of A_t h_{t-1}: the eight lanes' products on the exponent n_i + G
-        const int G = C::imax(C::imax(fa.x, fa.y), C::imax(fa.z, fa.w));
-        const int down = fsrc - G;
-        float part = sv[0] * hm[0];
-        part = __builtin_fmaf(sv[1], hm[1], part);
-        part = __builtin_fmaf(sv[2], hm[2], part);
-        part = __builtin_fmaf(sv[3], hm[3], part);
-        part = __builtin_ldexpf(part, down > -300 ? down : -300);
+        f4 sv;
+        int n, G;
+        float part;
+        if constexpr (ADJ) {
+            // ---- row i of A^T h: the lane's entries j = 4 cq .. 4 cq + 3 of column i, and of the vector with the rows' shifts
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sv[e] = s.sv[ms][(4 * cq + e) * (D + 1) + row];
+            const int4 nj = *reinterpret_cast<const int4 *>(&s.nsrc[ms][4 * cq]);
+            const int ej[4] = {nj.x + fsrc, nj.y + fsrc, nj.z + fsrc, nj.w + fsrc};
+            int g = C::imax(C::imax(ej[0], ej[1]), C::imax(ej[2], ej[3]));
+            g = C::imax(g, C::dpp<0xB1>(g));
+            g = C::imax(g, C::dpp<0x4E>(g));
+            g = C::imax(g, C::dpp<0x141>(g)); // the row's eight lanes cover all entries of the vector
+            G = g;
+            n = 0;
+            part = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int down = ej[e] - G;
+                part = __builtin_fmaf(sv[e], __builtin_ldexpf(hm[e], down > -300 ? down : -300), part);
+            }
+        } else {
+            // ---- row i of A_t h_{t-1}: the eight lanes' products on the exponent n_i + G
+            sv = *reinterpret_cast<const f4 *>(&s.sv[ms][row * D + 4 * cq]);
+            n = rec.x;
+            const int4 fa = *reinterpret_cast<const int4 *>(&s.f[rs][0]);
+            G = C::imax(C::imax(fa.x, fa.y), C::imax(fa.z, fa.w));
+            const int down = fsrc - G;
+            part = sv[0] * hm[0];
+            part = __builtin_fmaf(sv[1], hm[1], part);
+            part = __builtin_fmaf(sv[2], hm[2], part);
+            part = __builtin_fmaf(sv[3], hm[3], part);
+            part = __builtin_ldexpf(part, down > -300 ? down : -300);
+        }
         part = add_dpp<0xB1>(part);
         part = add_dpp<0x4E>(part);
         part = add_dpp<0x141>(part);
@@ -400,7 +419,7 @@ template <bool ADJ> __global__ __launch_bounds__(kSeqThreads) void affine_seq_ke
     if (wave < 4)
         seq_matrix_waves<ADJ>(a, s, wave, lane);
     else if (wave < 8)
-        seq_chain_waves(a, s, wave - 4, lane);
+        seq_chain_waves<ADJ>(a, s, wave - 4, lane);
     else
         seq_output_wave(a, s, lane);
 }
