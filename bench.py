@@ -453,6 +453,19 @@ def batched_lmme(g, torch, dev, si):
             "kernels_ms": kernel_times(g, lambda: g.lmme_backward(a, b, c, gc))}
         del a, b, c, gc
         torch.cuda.empty_cache()
+    # many rows against a small right operand: the input term of the state-space layer, bias_t = B u_t for all steps at once
+    # (8192 heads x 1024 steps, d = 32)
+    Bt, n, d = 8192, 1024, 32
+    u = g.to_goom(torch.randn((Bt, n, d), device=dev))
+    w = g.to_goom(torch.randn((Bt, d, d), device=dev))
+    c = torch.empty((Bt, n, d), dtype=torch.complex64, device=dev)
+    sec = timed(torch, lambda: g.lmme(u, w, flags=LMME_FAST, out=c))
+    res["lmme_tall_8192x1024x32x32"] = {
+        "ms": round(sec * 1e3, 3), "tflops": round(2.0 * n * d * d * Bt / sec / 1e12, 2),
+        "hbm_gbs": round((u.numel() + w.numel() + c.numel()) * 8 / sec / 1e9, 1),
+        "kernels_ms": kernel_times(g, lambda: g.lmme(u, w, flags=LMME_FAST, out=c))}
+    del u, w, c
+    torch.cuda.empty_cache()
     return res
 
 
