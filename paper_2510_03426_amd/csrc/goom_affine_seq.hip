@@ -2,7 +2,7 @@
 // batches of many sequences: one workgroup walks one whole sequence, step after step, and reads every matrix once.
 //
 // With a hundred sequences or more there is no need to cut a sequence into chunks (whose products cost a matrix-matrix
-// product per step and a second pass over the matrices): a workgroup keeps eight steps of its sequence's matrices in
+// product per step and a second pass over the matrices): a workgroup keeps twelve steps of its sequence's matrices in
 // flight, which is enough outstanding memory traffic per compute unit, and a step is a matrix-vector product.  The
 // work of a step falls into a part that does not depend on the running vector and a chain that does, and the
 // waves of the workgroup are split accordingly, one wave of each kind per SIMD, so that the first fills the waits of
@@ -29,7 +29,9 @@ namespace goom_chain {
 
 namespace {
 
-constexpr int kSeqDepth = 8;          // steps of a sequence in flight
+constexpr int kSeqDepth = 8;          // steps written out per round of the chain waves' loop
+constexpr int kSeqRing = 12;          // steps of a sequence in flight (forward)
+constexpr int kSeqRingAdj = 10;       // ... adjoint recurrence (one register more per step and lane)
 constexpr int kSeqNone = -(1 << 28);  // exponent of a group of zeros
 constexpr int kSeqExpLimit = 1 << 27; // whole-number exponents are kept inside +- this
 constexpr int kSeqD = 32;
@@ -91,6 +93,14 @@ template <int NEWER> __device__ inline void wait_matrix_part_shift(f4 &x, f4 &y,
 }
 template <int NEWER> __device__ inline void wait_matrix_part(f4 &x, f4 &y, f2 &b) { asm volatile("s_waitcnt vmcnt(%3)" : "+v"(x), "+v"(y), "+v"(b) : "n"(NEWER) : "memory"); }
 
+template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 constexpr float kSeqHi = 1.44269502162933349609375f; // float nearest log2(e)
 constexpr float kSeqLo = 1.925963033500011e-8f;      // log2(e) - kSeqHi
 
@@ -113,8 +123,9 @@ __device__ inline float scaled_term(float re, float im, int f)
 // matrix for s = 0) and adds left_shift[s] to its log-magnitudes (-inf: a zero matrix).  The matrix is loaded and scaled as it is
 // stored, row by row (the same contiguous loads as in the forward pass); the chain reads it by columns, and the shift of a stored
 // row j goes with entry j of the vector.
-template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqArgs &a, SeqShared &s, int wave, int lane)
+template <bool ADJ, int DEPTH> __device__ __forceinline__ void seq_matrix_waves(const SeqArgs &a, SeqShared &s, int wave, int lane)
 {
+    static_assert(DEPTH % 2 == 0, "the LDS sets alternate with the step's place in a round");
     typedef Comp<float> C;
     constexpr int D = kSeqD;
     const long long T = a.T;
@@ -125,11 +136,11 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
     [[maybe_unused]] const float *shp = ADJ ? a.left_shift + item * (size_t)T : nullptr;
     const unsigned char *bp = a.bias + item * (size_t)T * (D * 8) + (size_t)row * 8;
 
-    // slot j mod kSeqDepth: the lane's four entries of the matrix of step j (and, for the adjoint recurrence, the step's shift)
-    f4 ra[kSeqDepth], rb[kSeqDepth];
-    [[maybe_unused]] float qs[kSeqDepth];
-    f2 bq[kSeqDepth]; // the bias of step j, entry `row`
-    constexpr int kNewer = (ADJ ? 4 : 3) * (kSeqDepth - 1); // loads issued after a slot's own until its turn comes again
+    // slot j mod DEPTH: the lane's four entries of the matrix of step j (and, for the adjoint recurrence, the step's shift)
+    f4 ra[DEPTH], rb[DEPTH];
+    [[maybe_unused]] float qs[DEPTH];
+    f2 bq[DEPTH]; // the bias of step j, entry `row`
+    constexpr int kNewer = (ADJ ? 4 : 3) * (DEPTH - 1); // loads issued after a slot's own until its turn comes again
     auto load_slot = [&](auto sc, long long j) { // factor of step j (past the end: the last one again)
         constexpr int k = decltype(sc)::value;
         const long long jj = j < T ? j : T - 1;
@@ -147,14 +158,7 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
         else
             wait_matrix_part<kNewer>(ra[k], rb[k], bq[k]);
     };
-    load_slot(std::integral_constant<int, 0>{}, 0);
-    load_slot(std::integral_constant<int, 1>{}, 1);
-    load_slot(std::integral_constant<int, 2>{}, 2);
-    load_slot(std::integral_constant<int, 3>{}, 3);
-    load_slot(std::integral_constant<int, 4>{}, 4);
-    load_slot(std::integral_constant<int, 5>{}, 5);
-    load_slot(std::integral_constant<int, 6>{}, 6);
-    load_slot(std::integral_constant<int, 7>{}, 7);
+    static_for<0, DEPTH>([&](auto sc) { load_slot(sc, decltype(sc)::value); });
 
     // the lane's four entries scaled by the row's power of two and signed, to LDS set `set`
     auto scale_rows = [&](auto sc, int set) {
@@ -202,54 +206,36 @@ template <bool ADJ> __device__ __forceinline__ void seq_matrix_waves(const SeqAr
     // the factor of step 0, before the chain's first step
     wait_slot(std::integral_constant<int, 0>{});
     scale_rows(std::integral_constant<int, 0>{}, 0);
-    load_slot(std::integral_constant<int, 0>{}, kSeqDepth);
+    load_slot(std::integral_constant<int, 0>{}, DEPTH);
     lds_barrier();
 
-    // while the chain takes step t: the factor of step t + 1 scaled.  u = t mod kSeqDepth picks the ring's
+    // while the chain takes step t: the factor of step t + 1 scaled.  u = t mod DEPTH picks the ring's
     // registers and the LDS sets at compile time
     auto step = [&](auto uc, auto prefetch, [[maybe_unused]] long long t) {
         constexpr int u = decltype(uc)::value;
         constexpr bool kPrefetch = decltype(prefetch)::value; // false after the last full round: the rest of the sequence has landed
-        constexpr int slot = (u + 1) % kSeqDepth;
+        constexpr int slot = (u + 1) % DEPTH;
         if constexpr (kPrefetch) wait_slot(std::integral_constant<int, slot>{});
         scale_rows(std::integral_constant<int, slot>{}, (u + 1) & 1); // (past the end: the last factor again, read by nobody)
-        // the registers are free: the factor of step t + 1 + kSeqDepth (every step of a full round issues its loads)
-        if constexpr (kPrefetch) load_slot(std::integral_constant<int, slot>{}, t + 1 + kSeqDepth);
+        // the registers are free: the factor of step t + 1 + DEPTH (every step of a full round issues its loads)
+        if constexpr (kPrefetch) load_slot(std::integral_constant<int, slot>{}, t + 1 + DEPTH);
         lds_barrier();
     };
-    static_assert(kSeqDepth == 8, "the steps are written out");
     long long tb = 0;
-    for (; tb + kSeqDepth <= T; tb += kSeqDepth) {
-        step(std::integral_constant<int, 0>{}, std::true_type{}, tb);
-        step(std::integral_constant<int, 1>{}, std::true_type{}, tb + 1);
-        step(std::integral_constant<int, 2>{}, std::true_type{}, tb + 2);
-        step(std::integral_constant<int, 3>{}, std::true_type{}, tb + 3);
-        step(std::integral_constant<int, 4>{}, std::true_type{}, tb + 4);
-        step(std::integral_constant<int, 5>{}, std::true_type{}, tb + 5);
-        step(std::integral_constant<int, 6>{}, std::true_type{}, tb + 6);
-        step(std::integral_constant<int, 7>{}, std::true_type{}, tb + 7);
-    }
+    for (; tb + DEPTH <= T; tb += DEPTH) static_for<0, DEPTH>([&](auto uc) { step(uc, std::true_type{}, tb + decltype(uc)::value); });
     // Everything still in flight lands before the last, partial round: from here on the compiler is free to reuse a ring register
     // that no step reads any more, and a load still on its way would overwrite whatever it put there.
-    asm volatile("s_waitcnt vmcnt(0)"
-                 : "+v"(ra[0]), "+v"(ra[1]), "+v"(ra[2]), "+v"(ra[3]), "+v"(ra[4]), "+v"(ra[5]), "+v"(ra[6]), "+v"(ra[7]), "+v"(rb[0]), "+v"(rb[1]),
-                   "+v"(rb[2]), "+v"(rb[3]), "+v"(rb[4]), "+v"(rb[5]), "+v"(rb[6]), "+v"(rb[7]), "+v"(bq[0]), "+v"(bq[1]), "+v"(bq[2]), "+v"(bq[3]),
-                   "+v"(bq[4]), "+v"(bq[5]), "+v"(bq[6]), "+v"(bq[7])
-                 :
-                 : "memory");
-    if constexpr (ADJ)
-        asm volatile("" // (the shifts pass the same point)
-                     : "+v"(qs[0]), "+v"(qs[1]), "+v"(qs[2]), "+v"(qs[3]), "+v"(qs[4]), "+v"(qs[5]), "+v"(qs[6]), "+v"(qs[7])
-                     :
-                     : "memory");
+    static_for<0, DEPTH>([&](auto sc) { // (every register of the ring passes a wait for all of them)
+        constexpr int k = decltype(sc)::value;
+        if constexpr (ADJ)
+            wait_matrix_part_shift<0>(ra[k], rb[k], bq[k], qs[k]);
+        else
+            wait_matrix_part<0>(ra[k], rb[k], bq[k]);
+    });
     const int rest = (int)(T - tb); // (the same for the whole workgroup)
-    if (rest > 0) step(std::integral_constant<int, 0>{}, std::false_type{}, tb);
-    if (rest > 1) step(std::integral_constant<int, 1>{}, std::false_type{}, tb + 1);
-    if (rest > 2) step(std::integral_constant<int, 2>{}, std::false_type{}, tb + 2);
-    if (rest > 3) step(std::integral_constant<int, 3>{}, std::false_type{}, tb + 3);
-    if (rest > 4) step(std::integral_constant<int, 4>{}, std::false_type{}, tb + 4);
-    if (rest > 5) step(std::integral_constant<int, 5>{}, std::false_type{}, tb + 5);
-    if (rest > 6) step(std::integral_constant<int, 6>{}, std::false_type{}, tb + 6);
+    static_for<0, DEPTH - 1>([&](auto uc) {
+        if (rest > decltype(uc)::value) step(uc, std::false_type{}, tb + decltype(uc)::value);
+    });
 }
 
 // ---- waves 4-7: the chain
@@ -417,7 +403,7 @@ template <bool ADJ> __global__ __launch_bounds__(kSeqThreads) void affine_seq_ke
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (wave < 4)
-        seq_matrix_waves<ADJ>(a, s, wave, lane);
+        seq_matrix_waves<ADJ, ADJ ? kSeqRingAdj : kSeqRing>(a, s, wave, lane);
     else if (wave < 8)
         seq_chain_waves<ADJ>(a, s, wave - 4, lane);
     else
