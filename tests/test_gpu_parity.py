@@ -496,7 +496,7 @@ def test_scan_beyond_float_range(G, oracle):
 @pytest.mark.parametrize("T,d,batch,chunk", [(64, 8, 2, 0), (300, 32, 3, 32), (100, 16, 1, 9), (1, 32, 2, 0), (257, 64, 1, 40),
                                              (1000, 32, 2, 5), (90, 128, 2, 16), (70, 100, 1, 0),
                                              # many sequences of d = 32: each walked start to end by one workgroup
-                                             (1, 32, 96, 0), (37, 32, 97, 0), (300, 32, 130, 0), (8, 32, 96, 0), (1000, 32, 100, 0)])
+                                             (1, 32, 96, 0), (37, 32, 97, 0), (300, 32, 130, 0), (8, 32, 96, 0), (1000, 32, 100, 0), (33, 32, 300, 0)])
 def test_affine_scan_matches_oracle(G, oracle, T, d, batch, chunk):
     A, b = si.recurrence_inputs(si.BASE_SEED + 50, batch, T, d)
     Az, bz = oracle.to_goom(A), oracle.to_goom(b)
